@@ -1,0 +1,19 @@
+"""CPU oracle for sliding window sums (fp64, naive).  TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
+this package.  It holds the plain definitions (Section 2.2 Eq. 3, Section 2.3,
+Section 2.5 of the paper) written out as loops in C (sws_ref.c) behind a ctypes
+wrapper that does argument marshalling only.  It imports nothing from the GPU
+package and the GPU package imports nothing from here.
+"""
+from .ref import (  # noqa: F401
+    OP_ADD,
+    OP_MAX,
+    OP_MIN,
+    build,
+    conv1d,
+    conv2d,
+    pool2d,
+    slide1d,
+    threads,
+)

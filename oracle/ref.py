@@ -1,0 +1,142 @@
+"""ctypes wrapper around oracle/sws_ref.c.  TEST INFRASTRUCTURE ONLY.
+
+Marshals numpy arrays to the C oracle and returns (y, abs_sum) as float64
+arrays.  No arithmetic of the method happens in this file.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+OP_ADD, OP_MAX, OP_MIN = 0, 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sws_ref.c")
+_LIB = os.path.join(_HERE, "libsws_ref.so")
+_lib = None
+
+
+def build(force=True):
+    """Compile sws_ref.c into libsws_ref.so with gcc (OpenMP over rows only)."""
+    if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC):
+        return _LIB
+    cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+           "-o", _LIB, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_i64, _i32, _f64 = ctypes.c_int64, ctypes.c_int32, ctypes.c_double
+_fp = ctypes.POINTER(ctypes.c_float)
+_dp = ctypes.POINTER(ctypes.c_double)
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        lib = ctypes.CDLL(_LIB)
+        lib.sws_ref_threads.restype = ctypes.c_int
+        lib.sws_ref_slide1d.restype = ctypes.c_int
+        lib.sws_ref_slide1d.argtypes = [ctypes.c_int, _fp, _dp, _dp, _i64, _i64, _i32, _f64]
+        lib.sws_ref_pool2d.restype = ctypes.c_int
+        lib.sws_ref_pool2d.argtypes = [ctypes.c_int, _fp, _dp, _dp, _i64, _i64, _i64, _i64,
+                                       _i32, _i32, _i32, _i32, _i32, _i32, _f64]
+        lib.sws_ref_conv1d.restype = ctypes.c_int
+        lib.sws_ref_conv1d.argtypes = [_fp, _fp, _dp, _dp, _i64, _i64, _i64, _i64,
+                                       _i32, _i32, _i32, _i32, _i32]
+        lib.sws_ref_conv2d.restype = ctypes.c_int
+        lib.sws_ref_conv2d.argtypes = [_fp, _fp, _dp, _dp, _i64, _i64, _i64, _i64, _i64,
+                                       _i32, _i32, _i32, _i32, _i32, _i32]
+        _lib = lib
+    return _lib
+
+
+def threads():
+    """Number of OpenMP threads the oracle will use."""
+    return int(_load().sws_ref_threads())
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.float32:
+        raise TypeError("oracle inputs must be float32 (the data the GPU path reads)")
+    return a
+
+
+def _ptr_f(a):
+    return a.ctypes.data_as(_fp)
+
+
+def _ptr_d(a):
+    return a.ctypes.data_as(_dp)
+
+
+def slide1d(op, x, w, scale=1.0):
+    """x: [rows, len] float32 -> (y, abs_sum), each [rows, len-w+1] float64 (Eq. 3)."""
+    x = _f32(x)
+    if x.ndim == 1:
+        x = x[None, :]
+    rows, length = x.shape
+    lo = length - w + 1
+    if lo < 1:
+        raise ValueError("w must satisfy 1 <= w <= len")
+    y = np.empty((rows, lo), np.float64)
+    s = np.empty((rows, lo), np.float64)
+    rc = _load().sws_ref_slide1d(op, _ptr_f(x), _ptr_d(y), _ptr_d(s), rows, length, w, float(scale))
+    if rc:
+        raise ValueError("sws_ref_slide1d rejected its arguments")
+    return y, s
+
+
+def pool2d(op, x, kh, kw, sh=1, sw=1, ph=0, pw=0, scale=1.0):
+    """x: [N, C, H, W] float32 -> (y, abs_sum) [N, C, Ho, Wo] float64."""
+    x = _f32(x)
+    n, c, h, wd = x.shape
+    ho = (h + 2 * ph - kh) // sh + 1
+    wo = (wd + 2 * pw - kw) // sw + 1
+    y = np.empty((n, c, ho, wo), np.float64)
+    s = np.empty((n, c, ho, wo), np.float64)
+    rc = _load().sws_ref_pool2d(op, _ptr_f(x), _ptr_d(y), _ptr_d(s), n, c, h, wd,
+                                kh, kw, sh, sw, ph, pw, float(scale))
+    if rc:
+        raise ValueError("sws_ref_pool2d rejected its arguments")
+    return y, s
+
+
+def conv1d(x, wgt, stride=1, pad=0, dilation=1, groups=1):
+    """x: [B, Cin, L], wgt: [Cout, Cin/groups, k] float32 -> (y, abs_sum) [B, Cout, Lo] float64."""
+    x = _f32(x)
+    wgt = _f32(wgt)
+    b, cin, length = x.shape
+    cout, cig, k = wgt.shape
+    if cig * groups != cin:
+        raise ValueError("wgt.shape[1] * groups must equal Cin")
+    lo = (length + 2 * pad - dilation * (k - 1) - 1) // stride + 1
+    y = np.empty((b, cout, lo), np.float64)
+    s = np.empty((b, cout, lo), np.float64)
+    rc = _load().sws_ref_conv1d(_ptr_f(x), _ptr_f(wgt), _ptr_d(y), _ptr_d(s), b, cin, length, cout,
+                                k, stride, pad, dilation, groups)
+    if rc:
+        raise ValueError("sws_ref_conv1d rejected its arguments")
+    return y, s
+
+
+def conv2d(x, wgt, sh=1, sw=1, ph=0, pw=0):
+    """x: [N, Cin, H, W], wgt: [Cout, Cin, kh, kw] float32 -> (y, abs_sum) [N, Cout, Ho, Wo] float64."""
+    x = _f32(x)
+    wgt = _f32(wgt)
+    n, cin, h, wd = x.shape
+    cout, cin2, kh, kw = wgt.shape
+    if cin2 != cin:
+        raise ValueError("wgt.shape[1] must equal Cin")
+    ho = (h + 2 * ph - kh) // sh + 1
+    wo = (wd + 2 * pw - kw) // sw + 1
+    y = np.empty((n, cout, ho, wo), np.float64)
+    s = np.empty((n, cout, ho, wo), np.float64)
+    rc = _load().sws_ref_conv2d(_ptr_f(x), _ptr_f(wgt), _ptr_d(y), _ptr_d(s), n, cin, h, wd, cout,
+                                kh, kw, sh, sw, ph, pw)
+    if rc:
+        raise ValueError("sws_ref_conv2d rejected its arguments")
+    return y, s

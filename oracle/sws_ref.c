@@ -1,0 +1,218 @@
+/*
+ * sws_ref — CPU oracle for sliding window sums.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the slow, obviously-correct definition that the GPU library is
+ * checked against.  It is never part of the product path: only the tests, the
+ * smoke check and the bench's cpu_baseline leg load it.  It shares no code,
+ * header, table or helper with the HIP kernels.
+ *
+ * Everything is the plain definition written out as nested loops, accumulated
+ * in fp64, on host pointers:
+ *
+ *   sws_ref_slide1d  Section 2.2, Eq. 3 (sliding window sum): every output is
+ *                    the left-to-right combination of exactly w inputs, so a
+ *                    row of length len has len-w+1 outputs ("valid").  Naive
+ *                    O(w*N), the cost the paper quotes for the direct method.
+ *   sws_ref_pool2d   Section 2.3 (pooling = sliding sum with + or max) taken to
+ *                    two dimensions as a direct kh x kw window scan, NOT as two
+ *                    separable passes, so that a separable GPU evaluation is
+ *                    checked against an independent formulation.  Taps that
+ *                    fall into the padding contribute the identity of the
+ *                    operator (they are skipped).
+ *   sws_ref_conv1d   Section 2.5 (convolution = sliding dot product, Eq. 4 per
+ *   sws_ref_conv2d   output): cross-correlation (no tap flip), zero padding by
+ *                    skipping out-of-range taps, accumulation order ci, kh, kw.
+ *
+ * The paper fixes no precision; fp64 accumulation of fp32 data leaves the
+ * oracle's own rounding (~1e-16 * sum|terms|) far below the fp32 tolerance
+ * the GPU results are held to.  max/min of fp32 values is exact in fp64.
+ *
+ * abs_sum (optional, may be NULL) receives sum|terms| per output, the scale
+ * of the tolerance |err| <= 1e-5 * sum|terms|.
+ *
+ * Rows / planes / images are independent; the only parallelism is an OpenMP
+ * "parallel for" over them.  Nothing here is tuned.
+ *
+ * Pins (tests/test_oracle_pins.py): hand-enumerated tiny cases, closed forms
+ * for constant and ramp inputs, prefix-sum differences, window membership for
+ * max, the paper's Vector Input algorithm emulated with a non-commutative
+ * operator, the dot-product-as-prefix-sum construction of Eq. 7-9, and
+ * cross-operator identities (all-ones taps, one-hot taps, rank-1 2-D taps,
+ * separability of pooling, strided = subsampled).
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { REF_ADD = 0, REF_MAX = 1, REF_MIN = 2 };
+
+int sws_ref_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* a (+) b with a the older (left) operand. */
+static double combine(int op, double a, double b)
+{
+    switch (op) {
+    case REF_ADD: return a + b;
+    case REF_MAX: return (a < b) ? b : a;
+    default:      return (b < a) ? b : a;
+    }
+}
+
+/* Eq. 3:  y[r,i] = scale * (x[r,i] (+) x[r,i+1] (+) ... (+) x[r,i+w-1]),  0 <= i <= len-w.
+ * x: rows*len floats.  y, abs_sum: rows*(len-w+1) doubles.  scale applies to ADD only. */
+int sws_ref_slide1d(int op, const float *x, double *y, double *abs_sum,
+                    int64_t rows, int64_t len, int32_t w, double scale)
+{
+    if (op < 0 || op > 2 || rows < 0 || len < 0 || w < 1 || w > len) return 1;
+    if (rows > 0 && (!x || !y)) return 1;
+    const int64_t lo = len - w + 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const float *xr = x + r * len;
+        for (int64_t i = 0; i < lo; ++i) {
+            double acc = (double)xr[i];
+            double mag = fabs((double)xr[i]);
+            for (int32_t j = 1; j < w; ++j) {
+                acc = combine(op, acc, (double)xr[i + j]);
+                mag += fabs((double)xr[i + j]);
+            }
+            if (op == REF_ADD) { acc *= scale; mag *= fabs(scale); }
+            y[r * lo + i] = acc;
+            if (abs_sum) abs_sum[r * lo + i] = mag;
+        }
+    }
+    return 0;
+}
+
+/* NCHW pooling by direct window scan.  Ho = (H + 2*ph - kh)/sh + 1, Wo likewise.
+ * Padding holds the identity of op, i.e. out-of-range taps are skipped.  ADD is
+ * multiplied by scale (average pooling that counts the padding: scale = 1/(kh*kw)). */
+int sws_ref_pool2d(int op, const float *x, double *y, double *abs_sum,
+                   int64_t N, int64_t C, int64_t H, int64_t W,
+                   int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                   int32_t ph, int32_t pw, double scale)
+{
+    if (op < 0 || op > 2 || N < 0 || C < 0 || H < 0 || W < 0) return 1;
+    if (kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0) return 1;
+    if (ph >= kh || pw >= kw) return 1;            /* no window may lie wholly in padding */
+    if (kh > H + 2 * (int64_t)ph || kw > W + 2 * (int64_t)pw) return 1;
+    const int64_t Ho = (H + 2 * (int64_t)ph - kh) / sh + 1;
+    const int64_t Wo = (W + 2 * (int64_t)pw - kw) / sw + 1;
+    const int64_t planes = N * C;
+    if (planes > 0 && (!x || !y)) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t p = 0; p < planes; ++p) {
+        const float *xp = x + p * H * W;
+        for (int64_t ho = 0; ho < Ho; ++ho) {
+            for (int64_t wo = 0; wo < Wo; ++wo) {
+                int first = 1;
+                double acc = 0.0, mag = 0.0;
+                for (int32_t a = 0; a < kh; ++a) {
+                    const int64_t h = ho * sh - ph + a;
+                    if (h < 0 || h >= H) continue;
+                    for (int32_t b = 0; b < kw; ++b) {
+                        const int64_t c = wo * sw - pw + b;
+                        if (c < 0 || c >= W) continue;
+                        const double v = (double)xp[h * W + c];
+                        acc = first ? v : combine(op, acc, v);
+                        mag += fabs(v);
+                        first = 0;
+                    }
+                }
+                if (op == REF_ADD) { acc *= scale; mag *= fabs(scale); }
+                y[(p * Ho + ho) * Wo + wo] = acc;
+                if (abs_sum) abs_sum[(p * Ho + ho) * Wo + wo] = mag;
+            }
+        }
+    }
+    return 0;
+}
+
+/* y[b,co,i] = sum_{ci in group(co)} sum_{t<k} wgt[co,ci,t] * x[b, g*Cin/groups + ci, i*stride + t*dilation - pad]
+ * x [B,Cin,L], wgt [Cout,Cin/groups,k], y [B,Cout,Lo], Lo = (L + 2*pad - dilation*(k-1) - 1)/stride + 1. */
+int sws_ref_conv1d(const float *x, const float *wgt, double *y, double *abs_sum,
+                   int64_t B, int64_t Cin, int64_t L, int64_t Cout,
+                   int32_t k, int32_t stride, int32_t pad, int32_t dilation, int32_t groups)
+{
+    if (B < 0 || Cin < 1 || L < 0 || Cout < 1 || k < 1 || stride < 1 || pad < 0 || dilation < 1 || groups < 1) return 1;
+    if (Cin % groups || Cout % groups) return 1;
+    const int64_t span = (int64_t)dilation * (k - 1) + 1;
+    if (span > L + 2 * (int64_t)pad) return 1;
+    const int64_t Lo = (L + 2 * (int64_t)pad - span) / stride + 1;
+    const int64_t cig = Cin / groups, cog = Cout / groups;
+    if (B > 0 && (!x || !wgt || !y)) return 1;
+    const int64_t units = B * Cout;
+#pragma omp parallel for schedule(static)
+    for (int64_t u = 0; u < units; ++u) {
+        const int64_t b = u / Cout, co = u % Cout, g = co / cog;
+        for (int64_t i = 0; i < Lo; ++i) {
+            double acc = 0.0, mag = 0.0;
+            for (int64_t ci = 0; ci < cig; ++ci) {
+                const float *xr = x + (b * Cin + g * cig + ci) * L;
+                const float *wr = wgt + (co * cig + ci) * k;
+                for (int32_t t = 0; t < k; ++t) {
+                    const int64_t j = i * stride + (int64_t)t * dilation - pad;
+                    if (j < 0 || j >= L) continue;
+                    const double term = (double)wr[t] * (double)xr[j];
+                    acc += term;
+                    mag += fabs(term);
+                }
+            }
+            y[u * Lo + i] = acc;
+            if (abs_sum) abs_sum[u * Lo + i] = mag;
+        }
+    }
+    return 0;
+}
+
+/* NCHW x, OIHW wgt, zero padding, no bias, groups = 1:
+ * y[n,co,ho,wo] = sum_ci sum_a sum_b wgt[co,ci,a,b] * x[n,ci,ho*sh - ph + a, wo*sw - pw + b]. */
+int sws_ref_conv2d(const float *x, const float *wgt, double *y, double *abs_sum,
+                   int64_t N, int64_t Cin, int64_t H, int64_t W, int64_t Cout,
+                   int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw)
+{
+    if (N < 0 || Cin < 1 || H < 0 || W < 0 || Cout < 1) return 1;
+    if (kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0) return 1;
+    if (kh > H + 2 * (int64_t)ph || kw > W + 2 * (int64_t)pw) return 1;
+    const int64_t Ho = (H + 2 * (int64_t)ph - kh) / sh + 1;
+    const int64_t Wo = (W + 2 * (int64_t)pw - kw) / sw + 1;
+    if (N > 0 && (!x || !wgt || !y)) return 1;
+    const int64_t units = N * Cout;
+#pragma omp parallel for schedule(static)
+    for (int64_t u = 0; u < units; ++u) {
+        const int64_t n = u / Cout, co = u % Cout;
+        for (int64_t ho = 0; ho < Ho; ++ho) {
+            for (int64_t wo = 0; wo < Wo; ++wo) {
+                double acc = 0.0, mag = 0.0;
+                for (int64_t ci = 0; ci < Cin; ++ci) {
+                    const float *xp = x + (n * Cin + ci) * H * W;
+                    const float *wp = wgt + (co * Cin + ci) * kh * kw;
+                    for (int32_t a = 0; a < kh; ++a) {
+                        const int64_t h = ho * sh - ph + a;
+                        if (h < 0 || h >= H) continue;
+                        for (int32_t b = 0; b < kw; ++b) {
+                            const int64_t c = wo * sw - pw + b;
+                            if (c < 0 || c >= W) continue;
+                            const double term = (double)wp[a * kw + b] * (double)xp[h * W + c];
+                            acc += term;
+                            mag += fabs(term);
+                        }
+                    }
+                }
+                y[(u * Ho + ho) * Wo + wo] = acc;
+                if (abs_sum) abs_sum[(u * Ho + ho) * Wo + wo] = mag;
+            }
+        }
+    }
+    return 0;
+}

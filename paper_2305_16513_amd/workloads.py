@@ -1,0 +1,92 @@
+"""Seeded synthetic inputs shaped like the paper's DNN-layer workloads.
+
+This module holds input generation only — none of the method's arithmetic —
+so that the GPU path and the CPU oracle can both be fed identical bits.  The
+paper measures on no public dataset (an unspecified "large 1-D input" and a
+scenario from a cited work); these five configurations stand in for them.
+
+All tensors are float32, finite, and never contain -0.0 (so that max/min have
+a unique bit pattern).  Generation is on the host with numpy's PCG64 so the
+same seed gives the same bits everywhere.
+"""
+from dataclasses import dataclass, field
+
+import numpy as np
+
+SEED_BASE = 2305165130  # + config number 1..5
+
+
+@dataclass(frozen=True)
+class Config:
+    cfg: int
+    name: str
+    x_shape: tuple
+    x_dist: str                 # "uniform" (U[-1,1]), "normal" (N(0,1)), "relu" (max(N(0,1),0))
+    wgt_shape: tuple = ()
+    wgt_std: float = 0.0
+    ops: tuple = field(default_factory=tuple)
+
+
+CONFIGS = {
+    1: Config(1, "cfg1_1d_single", (1, 1, 1048576), "uniform", (1, 1, 5), 1.0,
+              ("slide_add_w5", "slide_max_w5", "corr_k5")),
+    2: Config(2, "cfg2_1d_multichannel", (16, 64, 4096), "normal", (64, 64, 3), (2.0 / (64 * 3)) ** 0.5,
+              ("avgpool_w3", "maxpool_w3", "conv1d_k3")),
+    3: Config(3, "cfg3_pool2d", (32, 64, 112, 112), "normal", (), 0.0,
+              ("maxpool3x3_s1", "avgpool3x3_s1", "maxpool3x3_s2", "avgpool3x3_s2")),
+    4: Config(4, "cfg4_conv2d_resnet", (32, 64, 56, 56), "relu", (64, 64, 3, 3), (2.0 / (64 * 9)) ** 0.5,
+              ("conv2d_3x3_p1",)),
+    5: Config(5, "cfg5_large_window_1d", (256, 128, 16384), "uniform", (128, 1, 31), (1.0 / 31.0) ** 0.5,
+              ("slide_add_w16", "slide_max_w16", "slide_add_w64", "slide_max_w64",
+               "slide_add_w255", "slide_max_w255", "dwconv_k31")),
+}
+
+
+def _draw(rng, shape, dist):
+    if dist == "uniform":
+        a = rng.random(shape, dtype=np.float32)
+        a *= np.float32(2.0)
+        a -= np.float32(1.0)
+    elif dist in ("normal", "relu"):
+        a = rng.standard_normal(shape, dtype=np.float32)
+        if dist == "relu":
+            np.maximum(a, np.float32(0.0), out=a)
+    else:
+        raise ValueError(dist)
+    a += np.float32(0.0)          # turns any -0.0 into +0.0
+    return a
+
+
+def check_clean(a):
+    """Raise if `a` holds NaN/inf or a negative zero."""
+    if not np.isfinite(a).all():
+        raise ValueError("non-finite synthetic input")
+    if np.any((a == 0) & np.signbit(a)):
+        raise ValueError("-0.0 in synthetic input")
+
+
+def make(cfg, x_shape=None, wgt_shape=None, seed_offset=0):
+    """Return (x, wgt) for configuration `cfg` (wgt is None where the config has none).
+
+    `x_shape` / `wgt_shape` override the full-size shapes with the same
+    distributions, for reduced parity cases.  Sub-streams are spawned in the
+    fixed order x, weights.
+    """
+    c = CONFIGS[cfg]
+    ss = np.random.SeedSequence(SEED_BASE + cfg + 1000 * seed_offset)
+    sx, sw = ss.spawn(2)
+    x = _draw(np.random.Generator(np.random.PCG64(sx)), tuple(x_shape or c.x_shape), c.x_dist)
+    wgt = None
+    shape_w = tuple(wgt_shape or c.wgt_shape)
+    if shape_w:
+        wgt = np.random.Generator(np.random.PCG64(sw)).standard_normal(shape_w, dtype=np.float32)
+        wgt *= np.float32(c.wgt_std)
+        wgt += np.float32(0.0)
+    return x, wgt
+
+
+def integer_valued(shape, lo, hi, seed):
+    """Small-integer-valued float32 tensor: every fp32 partial sum is exact, so
+    add/conv results can be compared bit for bit."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    return rng.integers(lo, hi + 1, size=shape).astype(np.float32)

@@ -1,0 +1,470 @@
+"""Pins for the CPU oracle: everything here checks oracle/ against something other
+than itself — hand-enumerated values, closed forms, invariants, the paper's own
+algorithms emulated step by step, and library routines as a third opinion.
+
+The paper prints no worked numeric example, so there are no paper-printed values
+to match; Fig. 1 / Fig. 2 speedups are "parity unpinned" (they need the authors'
+CPU and baseline library).
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import OP_ADD, OP_MAX, OP_MIN
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "slide_hand_cases.txt")
+OPS = {"add": OP_ADD, "max": OP_MAX, "min": OP_MIN}
+
+
+def _rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+# ----------------------------------------------------------------------------- P1
+def _hand_cases():
+    out = []
+    with open(GOLDEN) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            op, w, xs, ys = [p.strip() for p in line.split(";")]
+            out.append((op, int(w), [float(v) for v in xs.split()], [float(v) for v in ys.split()]))
+    return out
+
+
+@pytest.mark.parametrize("op,w,xs,ys", _hand_cases())
+def test_hand_enumerated(op, w, xs, ys):
+    """Section 2.2 Eq. 3 on tiny inputs worked out by hand (tests/golden)."""
+    y, _ = oracle.slide1d(OPS[op], np.array(xs, np.float32), w)
+    assert y.shape == (1, len(xs) - w + 1)
+    assert y[0].tolist() == ys
+
+
+def test_output_count_and_w_equals_len():
+    """Exactly w addends per output => len-w+1 outputs; w = len is the full reduction (Eq. 1 last element)."""
+    x = _rng(1).integers(-9, 10, size=(3, 17)).astype(np.float32)
+    for w in (1, 2, 16, 17):
+        y, _ = oracle.slide1d(OP_ADD, x, w)
+        assert y.shape == (3, 17 - w + 1)
+    y, _ = oracle.slide1d(OP_ADD, x, 17)
+    assert y[:, 0].tolist() == x.astype(np.float64).sum(axis=1).tolist()
+    with pytest.raises(ValueError):
+        oracle.slide1d(OP_ADD, x, 18)
+    with pytest.raises(ValueError):
+        oracle.slide1d(OP_ADD, x, 0)
+
+
+def test_rows_do_not_bleed():
+    """Each row is its own sequence: a window never crosses from one row into the next."""
+    x = np.array([[1, 2, 3, 4], [100, 200, 300, 400]], np.float32)
+    y, _ = oracle.slide1d(OP_ADD, x, 3)
+    assert y.tolist() == [[6, 9], [600, 900]]
+    y, _ = oracle.slide1d(OP_MAX, x, 2)
+    assert y.tolist() == [[2, 3, 4], [200, 300, 400]]
+
+
+# ----------------------------------------------------------------------------- P2
+@pytest.mark.parametrize("w", [1, 2, 5, 16, 255])
+def test_constant_closed_form(w):
+    c = 3.0
+    x = np.full((2, 300), c, np.float32)
+    y, s = oracle.slide1d(OP_ADD, x, w)
+    assert np.all(y == w * c) and np.all(s == w * c)
+    y, _ = oracle.slide1d(OP_MAX, x, w)
+    assert np.all(y == c)
+    y, _ = oracle.slide1d(OP_MIN, x, w)
+    assert np.all(y == c)
+    y, _ = oracle.slide1d(OP_ADD, x, w, scale=0.5)
+    assert np.all(y == 0.5 * w * c)
+
+
+def test_pool2d_constant_border_counts():
+    """3x3, pad 1 on a constant plane: interior sees 9 cells, an edge 6, a corner 4."""
+    c = 2.0
+    x = np.full((1, 2, 6, 7), c, np.float32)
+    y, _ = oracle.pool2d(OP_ADD, x, 3, 3, 1, 1, 1, 1, scale=1.0)
+    assert y.shape == (1, 2, 6, 7)
+    assert y[0, 0, 0, 0] == 4 * c and y[0, 1, 5, 6] == 4 * c and y[0, 0, 0, 6] == 4 * c
+    assert y[0, 0, 0, 3] == 6 * c and y[0, 0, 2, 0] == 6 * c and y[0, 0, 5, 2] == 6 * c
+    assert np.all(y[:, :, 1:-1, 1:-1] == 9 * c)
+    y, _ = oracle.pool2d(OP_ADD, x, 3, 3, 1, 1, 1, 1, scale=1.0 / 8.0)
+    assert y[0, 0, 0, 0] == 4 * c / 8 and y[0, 0, 2, 2] == 9 * c / 8
+    # max with identity padding: padding never wins, even on an all-negative plane
+    y, _ = oracle.pool2d(OP_MAX, -x, 3, 3, 1, 1, 1, 1)
+    assert np.all(y == -c)
+    y, _ = oracle.pool2d(OP_MIN, x, 3, 3, 1, 1, 1, 1)
+    assert np.all(y == c)
+
+
+def test_conv_constant_closed_form():
+    """Constant input c: every valid output equals c * sum of taps."""
+    taps = np.array([[[1, -2, 4, 8, -16]]], np.float32)
+    x = np.full((1, 1, 40), 3.0, np.float32)
+    y, s = oracle.conv1d(x, taps)
+    assert np.all(y == 3.0 * taps.sum()) and np.all(s == 3.0 * np.abs(taps).sum())
+    w2 = np.arange(1, 19, dtype=np.float32).reshape(1, 2, 3, 3)
+    x2 = np.full((1, 2, 5, 5), 2.0, np.float32)
+    y, _ = oracle.conv2d(x2, w2)
+    assert y.shape == (1, 1, 3, 3) and np.all(y == 2.0 * w2.sum())
+
+
+# ----------------------------------------------------------------------------- P3
+@pytest.mark.parametrize("w", [2, 5, 31])
+@pytest.mark.parametrize("b", [3, -2])
+def test_ramp_closed_form(w, b):
+    a, n = 7, 200
+    j = np.arange(n, dtype=np.float64)
+    x = (a + b * j).astype(np.float32)
+    i = np.arange(n - w + 1, dtype=np.float64)
+    y, _ = oracle.slide1d(OP_ADD, x, w)
+    assert np.all(y[0] == w * a + b * (w * i + w * (w - 1) / 2))
+    y, _ = oracle.slide1d(OP_MAX, x, w)
+    assert np.all(y[0] == (a + b * (i + w - 1) if b > 0 else a + b * i))
+    y, _ = oracle.slide1d(OP_MIN, x, w)
+    assert np.all(y[0] == (a + b * i if b > 0 else a + b * (i + w - 1)))
+
+
+# ----------------------------------------------------------------------------- P4
+@pytest.mark.parametrize("w", [1, 3, 16, 64, 255])
+def test_add_equals_prefix_sum_difference_exact(w):
+    """Integer-valued data: y_i = S_{i+w} - S_i exactly, and y_{i+1} = y_i - x_i + x_{i+w}."""
+    x = _rng(w).integers(-50, 51, size=(4, 700)).astype(np.float32)
+    y, s = oracle.slide1d(OP_ADD, x, w)
+    S = np.concatenate([np.zeros((4, 1)), np.cumsum(x.astype(np.float64), axis=1)], axis=1)
+    assert np.array_equal(y, S[:, w:] - S[:, :-w])
+    assert np.array_equal(y[:, 1:], y[:, :-1] - x[:, :-w] + x[:, w:])
+    A = np.concatenate([np.zeros((4, 1)), np.cumsum(np.abs(x).astype(np.float64), axis=1)], axis=1)
+    assert np.array_equal(s, A[:, w:] - A[:, :-w])
+
+
+@pytest.mark.parametrize("w", [3, 16, 255])
+def test_add_prefix_difference_real_valued(w):
+    x = (_rng(10 + w).random((2, 1000), dtype=np.float32) * 2 - 1).astype(np.float32)
+    y, s = oracle.slide1d(OP_ADD, x, w, scale=1.0 / w)
+    S = np.concatenate([np.zeros((2, 1)), np.cumsum(x.astype(np.float64), axis=1)], axis=1)
+    assert np.allclose(y * w, S[:, w:] - S[:, :-w], rtol=0, atol=1e-11)
+    assert np.all(s > 0)
+
+
+@pytest.mark.parametrize("w", [2, 5, 64])
+@pytest.mark.parametrize("op", [OP_MAX, OP_MIN])
+def test_extremum_membership_and_bound(op, w):
+    """max: y_i >= every element of its window and is one of them (min mirrored)."""
+    x = _rng(100 + w).standard_normal((3, 400), dtype=np.float32)
+    y, _ = oracle.slide1d(op, x, w)
+    win = np.lib.stride_tricks.sliding_window_view(x.astype(np.float64), w, axis=1)
+    if op == OP_MAX:
+        assert np.all(y[..., None] >= win)
+    else:
+        assert np.all(y[..., None] <= win)
+    assert np.all((y[..., None] == win).any(axis=-1))
+    # exact in fp32 too: converting back loses nothing
+    assert np.array_equal(y.astype(np.float32).astype(np.float64), y)
+
+
+# ----------------------------------------------------------------------------- P5
+def test_conv_all_ones_taps_is_sliding_add():
+    x = _rng(5).integers(-20, 21, size=(2, 3, 90)).astype(np.float32)
+    for k in (1, 3, 8):
+        taps = np.ones((3, 1, k), np.float32)
+        yc, _ = oracle.conv1d(x, taps, groups=3)
+        ys, _ = oracle.slide1d(OP_ADD, x.reshape(6, 90), k)
+        assert np.array_equal(yc.reshape(6, -1), ys)
+
+
+def test_conv_one_hot_tap_is_shift_no_flip():
+    """A one-hot tap e_t picks x[i+t]: cross-correlation, taps are NOT reversed."""
+    x = _rng(6).integers(-20, 21, size=(1, 1, 50)).astype(np.float32)
+    k = 5
+    for t in range(k):
+        taps = np.zeros((1, 1, k), np.float32)
+        taps[0, 0, t] = 1
+        y, _ = oracle.conv1d(x, taps)
+        assert np.array_equal(y[0, 0], x[0, 0, t:t + 50 - k + 1].astype(np.float64))
+
+
+def test_conv_linearity():
+    r = _rng(7)
+    x1 = r.integers(-9, 10, size=(2, 3, 40)).astype(np.float32)
+    x2 = r.integers(-9, 10, size=(2, 3, 40)).astype(np.float32)
+    w1 = r.integers(-4, 5, size=(4, 3, 3)).astype(np.float32)
+    w2 = r.integers(-4, 5, size=(4, 3, 3)).astype(np.float32)
+    f = lambda x, w: oracle.conv1d(x, w, stride=2, pad=1)[0]
+    assert np.array_equal(f(x1 + x2, w1), f(x1, w1) + f(x2, w1))
+    assert np.array_equal(f(x1, w1 + w2), f(x1, w1) + f(x1, w2))
+
+
+def test_conv1d_channels_sum_and_groups():
+    """groups=1 sums over input channels; depthwise equals each channel convolved alone."""
+    r = _rng(8)
+    x = r.integers(-9, 10, size=(2, 4, 30)).astype(np.float32)
+    w = r.integers(-4, 5, size=(3, 4, 5)).astype(np.float32)
+    y, _ = oracle.conv1d(x, w)
+    acc = np.zeros_like(y)
+    for ci in range(4):
+        acc += oracle.conv1d(x[:, ci:ci + 1], w[:, ci:ci + 1])[0]
+    assert np.array_equal(y, acc)
+    wd = r.integers(-4, 5, size=(4, 1, 5)).astype(np.float32)
+    yd, _ = oracle.conv1d(x, wd, groups=4)
+    for c in range(4):
+        assert np.array_equal(yd[:, c:c + 1], oracle.conv1d(x[:, c:c + 1], wd[c:c + 1])[0])
+
+
+def test_conv1d_padding_stride_dilation_by_hand():
+    x = np.array([[[1, 2, 3, 4, 5, 6]]], np.float32)
+    w = np.array([[[1, 10, 100]]], np.float32)
+    assert oracle.conv1d(x, w)[0][0, 0].tolist() == [321, 432, 543, 654]
+    assert oracle.conv1d(x, w, pad=1)[0][0, 0].tolist() == [210, 321, 432, 543, 654, 65]
+    assert oracle.conv1d(x, w, stride=2)[0][0, 0].tolist() == [321, 543]
+    assert oracle.conv1d(x, w, dilation=2)[0][0, 0].tolist() == [531, 642]
+    assert oracle.conv1d(x, w, stride=2, pad=2, dilation=2)[0][0, 0].tolist() == [310, 531, 53]
+
+
+def test_conv2d_rank1_taps_separate():
+    """Taps u v^T: 2-D correlation = 1-D along W with v, then 1-D along H with u."""
+    r = _rng(9)
+    x = r.integers(-9, 10, size=(1, 1, 9, 11)).astype(np.float32)
+    u = np.array([1, -2, 3], np.float32)
+    v = np.array([2, 0, -1, 4], np.float32)
+    w2 = np.outer(u, v).reshape(1, 1, 3, 4).astype(np.float32)
+    y2, _ = oracle.conv2d(x, w2)
+    rows = oracle.conv1d(x.reshape(9, 1, 11), v.reshape(1, 1, 4))[0].reshape(9, 8)
+    cols = oracle.conv1d(np.ascontiguousarray(rows.T.astype(np.float32)).reshape(8, 1, 9), u.reshape(1, 1, 3))[0]
+    assert np.array_equal(y2[0, 0], cols.reshape(8, 7).T)
+
+
+def test_conv2d_asymmetric_by_hand():
+    """kh != kw, H != W, distinct strides/pads: catches swapped H/W indices."""
+    x = np.arange(1, 13, dtype=np.float32).reshape(1, 1, 3, 4)
+    w = np.array([[[[1, 10]]]], np.float32)          # kh=1, kw=2
+    y, _ = oracle.conv2d(x, w)
+    assert y[0, 0].tolist() == [[21, 32, 43], [65, 76, 87], [109, 120, 131]]
+    y, _ = oracle.conv2d(x, w, sh=2, sw=1, ph=0, pw=1)
+    assert y[0, 0].tolist() == [[10, 21, 32, 43, 4], [90, 109, 120, 131, 12]]
+    wt = np.array([[[[1], [10]]]], np.float32)       # kh=2, kw=1
+    y, _ = oracle.conv2d(x, wt)
+    assert y[0, 0].tolist() == [[51, 62, 73, 84], [95, 106, 117, 128]]
+
+
+@pytest.mark.parametrize("op", [OP_ADD, OP_MAX, OP_MIN])
+def test_pool2d_is_separable_sliding_sums(op):
+    """pool2d (no padding) = slide1d down H then along W."""
+    x = _rng(11).integers(-30, 31, size=(2, 2, 10, 13)).astype(np.float32)
+    kh, kw = 3, 4
+    y, _ = oracle.pool2d(op, x, kh, kw)
+    cols = np.ascontiguousarray(x.transpose(0, 1, 3, 2)).reshape(-1, 10)       # rows of H
+    v = oracle.slide1d(op, cols, kh)[0].reshape(2, 2, 13, 8).transpose(0, 1, 3, 2)
+    h = oracle.slide1d(op, np.ascontiguousarray(v).astype(np.float32).reshape(-1, 13), kw)[0]
+    assert np.array_equal(y, h.reshape(2, 2, 8, 10))
+
+
+@pytest.mark.parametrize("op", [OP_ADD, OP_MAX])
+def test_pool2d_stride2_is_subsampled_stride1(op):
+    x = _rng(12).integers(-30, 31, size=(1, 3, 12, 14)).astype(np.float32)
+    y1, _ = oracle.pool2d(op, x, 3, 3, 1, 1, 1, 1)
+    y2, _ = oracle.pool2d(op, x, 3, 3, 2, 2, 1, 1)
+    assert y2.shape == (1, 3, 6, 7)
+    assert np.array_equal(y2, y1[:, :, ::2, ::2])
+
+
+def test_pool2d_padding_matches_explicit_identity_padding():
+    x = _rng(13).integers(-30, 31, size=(1, 2, 7, 9)).astype(np.float32)
+    for op, ident in ((OP_ADD, 0.0), (OP_MAX, -1e30), (OP_MIN, 1e30)):
+        xp = np.full((1, 2, 7 + 4, 9 + 2), ident, np.float32)
+        xp[:, :, 2:-2, 1:-1] = x
+        a, _ = oracle.pool2d(op, x, 4, 3, 2, 1, 2, 1)
+        b, _ = oracle.pool2d(op, xp, 4, 3, 2, 1, 0, 0)
+        assert np.array_equal(a, b)
+
+
+# ----------------------------------------------------------------------------- P6
+def _brute(op2, x, w):
+    """Eq. 3 written out in pure Python for an arbitrary binary operator."""
+    out = []
+    for i in range(len(x) - w + 1):
+        acc = x[i]
+        for j in range(1, w):
+            acc = op2(acc, x[i + j])
+        out.append(acc)
+    return out
+
+
+def _vector_input(op2, ident, x, w, P):
+    """Section 3, Algorithm 2 (Vector Input) with vectors of width P > w.
+
+    Reading used: the carry Y holds, in lanes 0..w-2, the suffix sums of the last
+    w-1 inputs seen (w-1, w-2, ..., 1 terms, each ending at the newest input);
+    X1[t] is the prefix sum of the new vector ending at lane t with at most w
+    terms; the outputs are Y (+) X1, and lanes whose window is entirely inside
+    the new vector take X1 alone (Y holds the identity there).
+    """
+    N = len(x)
+    assert P > w and N >= w
+
+    def suffixes(vals):            # suffix sums of the last w-1 values, longest first
+        out = []
+        for s in range(len(vals) - (w - 1), len(vals)):
+            acc = vals[s]
+            for v in vals[s + 1:]:
+                acc = op2(acc, v)
+            out.append(acc)
+        return out
+
+    y = []
+    Y = suffixes(x[:w - 1]) if w > 1 else []
+    i = w - 1
+    while i < N:
+        X = x[i:i + P]
+        X1 = []
+        for t in range(len(X)):
+            lo = max(0, t - (w - 1))
+            acc = X[lo]
+            for v in X[lo + 1:t + 1]:
+                acc = op2(acc, v)
+            X1.append(acc)
+        for t in range(len(X)):
+            y.append(op2(Y[t], X1[t]) if t < len(Y) else X1[t])
+        if w > 1:
+            tail = (x[max(0, i - (w - 1)):i] + X)[-(w - 1):]
+            Y = suffixes(tail)
+        i += P
+    return y
+
+
+def _segment_scheme(op2, x, w):
+    """Block form of the same idea: segments of length S = w-1 from the origin,
+    Pre = in-segment prefix sums, Suf = in-segment suffix sums, and
+    y_i = Suf[i] (+) Pre[i+w-1] — one combination per output, older operand left."""
+    N, S = len(x), w - 1
+    if S == 0:
+        return list(x)
+    pre, suf = list(x), list(x)
+    for j in range(N):
+        if j % S:
+            pre[j] = op2(pre[j - 1], x[j])
+    for j in range(N - 1, -1, -1):
+        if (j + 1) % S and j + 1 < N:
+            suf[j] = op2(x[j], suf[j + 1])
+    return [op2(suf[i], pre[i + S]) for i in range(N - w + 1)]
+
+
+def test_paper_algorithms_noncommutative():
+    """Vector Input (Alg. 2) and the segment prefix/suffix scheme reproduce Eq. 3 for
+    string concatenation, which is associative but not commutative — so operand
+    order and every index of the reading are pinned."""
+    cat = lambda a, b: a + b
+    for N, w in itertools.product((7, 16, 33, 64), range(1, 9)):
+        if w > N:
+            continue
+        x = [chr(ord("a") + (i * 7 + 3) % 26) + str(i % 10) for i in range(N)]
+        want = _brute(cat, x, w)
+        assert _segment_scheme(cat, x, w) == want
+        for P in (w + 1, 9, 16):
+            if P > w:
+                assert _vector_input(cat, "", x, w, P) == want
+
+
+@pytest.mark.parametrize("w", [2, 3, 7, 12])
+def test_paper_algorithms_agree_with_c_oracle(w):
+    """The emulated algorithms, run on integer-valued floats, equal the C oracle exactly."""
+    x = _rng(20 + w).integers(-40, 41, size=61).astype(np.float32)
+    xs = [float(v) for v in x]
+    for op, f in ((OP_ADD, lambda a, b: a + b), (OP_MAX, max), (OP_MIN, min)):
+        y, _ = oracle.slide1d(op, x, w)
+        assert _vector_input(f, None, xs, w, 16) == y[0].tolist()
+        assert _segment_scheme(f, xs, w) == y[0].tolist()
+
+
+# ----------------------------------------------------------------------------- P7
+def _gamma_dot(a, b):
+    """Section 2.4: dot product as a prefix sum.  Mask (Eq. 5), build the M+1 pairs
+    (u_i, v_i) of Eq. 7, fold them with the operator of Eq. 8 (Eq. 9); the bottom
+    element of the last sum is the dot product."""
+    M = len(a)
+    al = [1.0 if ai == 0 else float(ai) for ai in a]
+    be = [0.0 if ai == 0 else float(bi) for ai, bi in zip(a, b)]
+    g = []
+    for i in range(M + 1):
+        if i == 0:
+            u = 1.0
+        elif i < M:
+            u = al[i - 1] / al[i]
+        else:
+            u = al[M - 1]
+        v = be[i] if i < M else 0.0
+        g.append((u, v))
+    comb = lambda p, q: (p[0] * q[0], q[0] * p[1] + q[1])
+    left = g[0]
+    for q in g[1:]:
+        left = comb(left, q)
+    # associativity: a balanced bracketing gives the same bottom element
+    def tree(lo, hi):
+        if hi - lo == 1:
+            return g[lo]
+        mid = (lo + hi) // 2
+        return comb(tree(lo, mid), tree(mid, hi))
+    return left[1], tree(0, M + 1)[1]
+
+
+@pytest.mark.parametrize("k", [1, 2, 5, 31])
+def test_dot_product_as_prefix_sum_matches_conv_oracle(k):
+    r = _rng(30 + k)
+    taps = r.standard_normal(k).astype(np.float32)
+    if k >= 5:
+        taps[[1, 3]] = 0.0                          # exercise the masking of Eq. 5
+    x = r.standard_normal(k).astype(np.float32)
+    y, s = oracle.conv1d(x.reshape(1, 1, k), taps.reshape(1, 1, k))
+    seq, tr = _gamma_dot(taps, x)
+    assert abs(seq - y[0, 0, 0]) <= 1e-11 * max(1.0, s[0, 0, 0])
+    assert abs(tr - y[0, 0, 0]) <= 1e-11 * max(1.0, s[0, 0, 0])
+
+
+# ----------------------------------------------------------------------------- P8
+def test_third_opinion_library_routines():
+    """fp64 library routines on small shapes — a third opinion, never the oracle."""
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    r = _rng(40)
+    x = r.standard_normal((2, 6, 37), dtype=np.float32)
+    w = r.standard_normal((4, 3, 5), dtype=np.float32)
+    for stride, pad, dil in ((1, 0, 1), (2, 3, 1), (1, 2, 3), (3, 1, 2)):
+        y, _ = oracle.conv1d(x, w, stride=stride, pad=pad, dilation=dil, groups=2)
+        t = F.conv1d(torch.from_numpy(x).double(), torch.from_numpy(w).double(), None, stride, pad, dil, 2)
+        assert np.allclose(y, t.numpy(), rtol=0, atol=1e-12)
+    x2 = r.standard_normal((2, 3, 11, 9), dtype=np.float32)
+    w2 = r.standard_normal((5, 3, 3, 2), dtype=np.float32)
+    for sh, sw, ph, pw in ((1, 1, 0, 0), (2, 1, 1, 1), (1, 3, 2, 0)):
+        y, _ = oracle.conv2d(x2, w2, sh, sw, ph, pw)
+        t = F.conv2d(torch.from_numpy(x2).double(), torch.from_numpy(w2).double(), None, (sh, sw), (ph, pw))
+        assert np.allclose(y, t.numpy(), rtol=0, atol=1e-12)
+    for kh, kw, sh, sw, ph, pw in ((3, 3, 1, 1, 1, 1), (3, 3, 2, 2, 1, 1), (2, 4, 1, 2, 1, 2), (5, 1, 2, 1, 2, 0)):
+        y, _ = oracle.pool2d(OP_ADD, x2, kh, kw, sh, sw, ph, pw, scale=1.0 / (kh * kw))
+        t = F.avg_pool2d(torch.from_numpy(x2).double(), (kh, kw), (sh, sw), (ph, pw), count_include_pad=True)
+        assert np.allclose(y, t.numpy(), rtol=0, atol=1e-12)
+        y, _ = oracle.pool2d(OP_MAX, x2, kh, kw, sh, sw, ph, pw)
+        t = F.max_pool2d(torch.from_numpy(x2).double(), (kh, kw), (sh, sw), (ph, pw))
+        assert np.array_equal(y, t.numpy())
+    y, _ = oracle.slide1d(OP_ADD, x.reshape(12, 37), 7, scale=1.0 / 7)
+    t = F.avg_pool1d(torch.from_numpy(x).double(), 7, 1)
+    assert np.allclose(y, t.numpy().reshape(12, -1), rtol=0, atol=1e-12)
+
+
+def test_abs_sum_is_sum_of_magnitudes():
+    r = _rng(50)
+    x = r.standard_normal((1, 3, 20), dtype=np.float32)
+    w = r.standard_normal((2, 3, 4), dtype=np.float32)
+    _, s = oracle.conv1d(x, w, pad=1)
+    y_abs, _ = oracle.conv1d(np.abs(x), np.abs(w), pad=1)
+    assert np.allclose(s, y_abs, rtol=1e-14, atol=0)
+    x2 = r.standard_normal((1, 2, 6, 6), dtype=np.float32)
+    w2 = r.standard_normal((2, 2, 3, 3), dtype=np.float32)
+    _, s = oracle.conv2d(x2, w2, 1, 1, 1, 1)
+    y_abs, _ = oracle.conv2d(np.abs(x2), np.abs(w2), 1, 1, 1, 1)
+    assert np.allclose(s, y_abs, rtol=1e-14, atol=0)
+    _, s = oracle.pool2d(OP_ADD, x2, 3, 3, 1, 1, 1, 1, scale=-0.25)
+    y_abs, _ = oracle.pool2d(OP_ADD, np.abs(x2), 3, 3, 1, 1, 1, 1, scale=0.25)
+    assert np.allclose(s, y_abs, rtol=1e-14, atol=0)
