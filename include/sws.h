@@ -1,0 +1,126 @@
+/*
+ * sws.h — C ABI of libsws: sliding window sums on one AMD MI355X (gfx950).
+ *
+ * Implements the hot path of "Sliding Window Sum Algorithms for Deep Neural
+ * Networks" (arXiv 2305.16513): the sliding window sum of Section 2.2 (Eq. 3)
+ * used as average / max pooling (Section 2.3) and as convolution that reads
+ * the unmodified input and never builds an im2col column matrix (Section 2.5).
+ *
+ * Conventions common to every entry point
+ *   - Every data pointer is DEVICE memory owned by the caller (fp32, densely
+ *     packed, row-major in the stated index order, 4-byte aligned; 16-byte
+ *     aligned bases are fastest).  Inputs are read-only and must not overlap
+ *     the output.  The library allocates nothing, frees nothing and keeps no
+ *     pointer after the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on it; calls are asynchronous and never synchronise.
+ *   - Errors are reported by return code only.  Arguments are checked before
+ *     anything is launched; a problem with zero outputs returns SWS_OK without
+ *     launching.  A failed launch returns SWS_ERR_HIP.
+ *   - Inputs are assumed finite.  NaN propagation through MAX / MIN is
+ *     unspecified, and so is the sign of a zero result when a MAX / MIN window
+ *     holds both +0.0 and -0.0.
+ *   - Reentrant; no mutable global state except the developer knobs of
+ *     sws_set_option().
+ */
+#ifndef SWS_H
+#define SWS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SWS_OK = 0,
+    SWS_ERR_INVALID_ARG = 1,   /* null pointer, bad size, window larger than input, overflow */
+    SWS_ERR_UNSUPPORTED = 2,   /* legal request that no kernel variant covers */
+    SWS_ERR_HIP = 3            /* the HIP runtime refused the launch */
+} sws_status;
+
+/* The associative operator (+) of Eq. 3.  ADD and MAX are pooling (Section 2.3);
+ * MIN is the paper's example of another associative operator (Section 3). */
+typedef enum { SWS_OP_ADD = 0, SWS_OP_MAX = 1, SWS_OP_MIN = 2 } sws_op;
+
+/* Sliding window sum, Section 2.2 Eq. 3, applied to `rows` independent sequences:
+ *
+ *   y[r, i] = scale * ( x[r,i] (+) x[r,i+1] (+) ... (+) x[r,i+w-1] ),   0 <= i <= len - w
+ *
+ * Every output combines exactly w inputs ("valid"), operands in index order.
+ *   x : device, rows*len floats          y : device, rows*(len-w+1) floats
+ *   scale multiplies ADD results (1/w gives 1-D average pooling); ignored for MAX / MIN.
+ * Errors: INVALID_ARG if op is unknown, rows < 0, len < 0, w < 1, w > len, a pointer is
+ * NULL while there is output, or a size overflows int64 / len exceeds 2^31-1. */
+sws_status sws_slide1d(sws_op op, const float *x, float *y, int64_t rows, int64_t len,
+                       int32_t w, float scale, void *stream);
+
+/* 2-D pooling (Section 2.3 extended to two dimensions) evaluated as separable sliding
+ * sums, first along H then along W, on NCHW data:
+ *
+ *   y[n,c,ho,wo] = scale * (+)_{a<kh} (+)_{b<kw} x[n,c, ho*sh - ph + a, wo*sw - pw + b]
+ *
+ * Ho = (H + 2*ph - kh)/sh + 1, Wo = (W + 2*pw - kw)/sw + 1 (floor).  Padding cells hold
+ * the identity of op (0 for ADD, -inf for MAX, +inf for MIN).  scale multiplies ADD
+ * results (1/(kh*kw) = average pooling that counts the padding); ignored for MAX / MIN.
+ *   x : device, N*C*H*W floats          y : device, N*C*Ho*Wo floats
+ * Errors: INVALID_ARG for unknown op, negative sizes, kh/kw/sh/sw < 1, ph/pw < 0,
+ * ph >= kh or pw >= kw (a window wholly inside padding), window larger than the padded
+ * input, NULL pointer with output, H or W above 2^31-1. */
+sws_status sws_pool2d(sws_op op, const float *x, float *y, int64_t N, int64_t C, int64_t H,
+                      int64_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                      int32_t ph, int32_t pw, float scale, void *stream);
+
+/* 1-D convolution as a sliding dot product (Section 2.5; Eq. 4 per output), in the DNN
+ * sense: cross-correlation, taps not flipped, zero padding, no bias.
+ *
+ *   y[b,co,i] = sum_{ci < Cin/groups} sum_{t < k}
+ *                 wgt[co,ci,t] * x[b, g*Cin/groups + ci, i*stride + t*dilation - pad]
+ *   g = co / (Cout/groups),  Lo = (L + 2*pad - dilation*(k-1) - 1)/stride + 1
+ *
+ *   x : device [B,Cin,L]    wgt : device [Cout,Cin/groups,k]    y : device [B,Cout,Lo]
+ * groups = 1 is the dense-channel contraction; groups = Cin = Cout is depthwise.
+ * Errors: INVALID_ARG for sizes < 0, Cin/Cout/k/stride/dilation/groups < 1, pad < 0,
+ * Cin or Cout not divisible by groups, kernel span above the padded length, NULL pointer
+ * with output, L above 2^31-1. */
+sws_status sws_conv1d(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin,
+                      int64_t L, int64_t Cout, int32_t k, int32_t stride, int32_t pad,
+                      int32_t dilation, int32_t groups, void *stream);
+
+/* 2-D convolution (same reading of Section 2.5 on NCHW x and OIHW wgt, groups = 1):
+ *
+ *   y[n,co,ho,wo] = sum_ci sum_{a<kh} sum_{b<kw} wgt[co,ci,a,b] * x[n,ci, ho*sh-ph+a, wo*sw-pw+b]
+ *
+ * Zero padding, no bias, no dilation.  Ho, Wo as for sws_pool2d.
+ *   x : device [N,Cin,H,W]   wgt : device [Cout,Cin,kh,kw]   y : device [N,Cout,Ho,Wo]
+ * Errors: as sws_conv1d. */
+sws_status sws_conv2d(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin,
+                      int64_t H, int64_t W, int64_t Cout, int32_t kh, int32_t kw,
+                      int32_t sh, int32_t sw, int32_t ph, int32_t pw, void *stream);
+
+/* Plain device-to-device copy of n floats with the same 128-bit access pattern the
+ * sliding kernels use.  Not part of the method: it measures the HBM ceiling a
+ * one-read-one-write kernel can reach on this device, and calibrates byte counters. */
+sws_status sws_copy(const float *src, float *dst, int64_t n, void *stream);
+
+/* Host helper: number of outputs of a sliding window of `w` taps spaced `dilation`
+ * apart over `len` inputs padded by `pad` on both sides, moved in steps of `stride`.
+ * Returns -1 if the arguments are invalid or no window fits. */
+int64_t sws_out_len(int64_t len, int32_t w, int32_t stride, int32_t pad, int32_t dilation);
+
+/* Static, never-freed description of a status code. */
+const char *sws_status_string(int status);
+
+/* Developer knobs for A/B measurements (not needed for normal use; not thread-safe).
+ * Known keys: "slide_variant", "pool2d_variant", "conv1d_variant", "conv2d_variant"
+ * (0 = automatic choice) and "slide_chunk".  Returns SWS_ERR_INVALID_ARG for an
+ * unknown key. */
+sws_status sws_set_option(const char *key, int64_t value);
+
+/* Library version, "major.minor". */
+const char *sws_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWS_H */

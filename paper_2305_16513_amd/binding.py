@@ -1,0 +1,174 @@
+"""ctypes binding of libsws.so — argument marshalling only.
+
+Every function mirrors one entry point of include/sws.h, takes torch tensors that live
+on the GPU (PyTorch is used for device memory and streams, nothing else), checks
+dtype / device / contiguity, and passes raw device pointers plus the current HIP stream
+to the C ABI.  There is no fallback: a missing library or a non-zero status raises.
+"""
+import ctypes
+import os
+
+import torch
+
+OP_ADD, OP_MAX, OP_MIN = 0, 1, 2
+SWS_OK, SWS_ERR_INVALID_ARG, SWS_ERR_UNSUPPORTED, SWS_ERR_HIP = 0, 1, 2, 3
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsws.so")
+_lib = None
+
+_i64, _i32, _f32, _vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
+
+EXPORTS = ("sws_slide1d", "sws_pool2d", "sws_conv1d", "sws_conv2d", "sws_copy", "sws_out_len",
+           "sws_status_string", "sws_set_option", "sws_version")
+
+
+class SwsError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (what, status_string(status), status))
+
+
+def lib():
+    """The loaded C library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                "%s is missing: build it with `python -m paper_2305_16513_amd.build`" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        L.sws_slide1d.restype = ctypes.c_int
+        L.sws_slide1d.argtypes = [ctypes.c_int, _vp, _vp, _i64, _i64, _i32, _f32, _vp]
+        L.sws_pool2d.restype = ctypes.c_int
+        L.sws_pool2d.argtypes = [ctypes.c_int, _vp, _vp, _i64, _i64, _i64, _i64,
+                                 _i32, _i32, _i32, _i32, _i32, _i32, _f32, _vp]
+        L.sws_conv1d.restype = ctypes.c_int
+        L.sws_conv1d.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _vp]
+        L.sws_conv2d.restype = ctypes.c_int
+        L.sws_conv2d.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64,
+                                 _i32, _i32, _i32, _i32, _i32, _i32, _vp]
+        L.sws_copy.restype = ctypes.c_int
+        L.sws_copy.argtypes = [_vp, _vp, _i64, _vp]
+        L.sws_out_len.restype = _i64
+        L.sws_out_len.argtypes = [_i64, _i32, _i32, _i32, _i32]
+        L.sws_status_string.restype = ctypes.c_char_p
+        L.sws_status_string.argtypes = [ctypes.c_int]
+        L.sws_set_option.restype = ctypes.c_int
+        L.sws_set_option.argtypes = [ctypes.c_char_p, _i64]
+        L.sws_version.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def status_string(status):
+    return lib().sws_status_string(int(status)).decode()
+
+
+def sws_version():
+    return lib().sws_version().decode()
+
+
+def sws_out_len(length, w, stride=1, pad=0, dilation=1):
+    return int(lib().sws_out_len(length, w, stride, pad, dilation))
+
+
+def sws_set_option(key, value):
+    rc = lib().sws_set_option(key.encode(), int(value))
+    if rc:
+        raise SwsError(rc, "sws_set_option(%r)" % key)
+
+
+def _dev(t, name):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a GPU tensor" % name)
+    if t.dtype != torch.float32 or not t.is_contiguous():
+        raise TypeError("%s must be contiguous float32" % name)
+    return t
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _out(y, shape, like, name="y"):
+    if y is None:
+        return torch.empty(shape, dtype=torch.float32, device=like.device)
+    _dev(y, name)
+    if tuple(y.shape) != tuple(shape):
+        raise ValueError("%s has shape %s, expected %s" % (name, tuple(y.shape), tuple(shape)))
+    return y
+
+
+def _check(rc, what):
+    if rc != SWS_OK:
+        raise SwsError(rc, what)
+
+
+def sws_slide1d(op, x, w, scale=1.0, y=None, stream=None):
+    """x [..., len] -> y [..., len-w+1]; all leading dimensions are independent rows."""
+    _dev(x, "x")
+    length = x.shape[-1]
+    rows = x.numel() // length if length else 0
+    lo = length - w + 1
+    if lo < 1 or w < 1:
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_slide1d")
+    y = _out(y, tuple(x.shape[:-1]) + (lo,), x)
+    _check(lib().sws_slide1d(op, x.data_ptr(), y.data_ptr(), rows, length, w, scale, _stream(stream)),
+           "sws_slide1d")
+    return y
+
+
+def sws_pool2d(op, x, kh, kw, sh=1, sw=1, ph=0, pw=0, scale=1.0, y=None, stream=None):
+    """x [N, C, H, W] -> y [N, C, Ho, Wo]."""
+    _dev(x, "x")
+    n, c, h, wd = x.shape
+    ho, wo = sws_out_len(h, kh, sh, ph), sws_out_len(wd, kw, sw, pw)
+    if ho < 1 or wo < 1:
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_pool2d")
+    y = _out(y, (n, c, ho, wo), x)
+    _check(lib().sws_pool2d(op, x.data_ptr(), y.data_ptr(), n, c, h, wd, kh, kw, sh, sw, ph, pw, scale,
+                            _stream(stream)), "sws_pool2d")
+    return y
+
+
+def sws_conv1d(x, wgt, stride=1, pad=0, dilation=1, groups=1, y=None, stream=None):
+    """x [B, Cin, L], wgt [Cout, Cin/groups, k] -> y [B, Cout, Lo]."""
+    _dev(x, "x")
+    _dev(wgt, "wgt")
+    b, cin, length = x.shape
+    cout, cig, k = wgt.shape
+    if cig * groups != cin:
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_conv1d")
+    lo = sws_out_len(length, k, stride, pad, dilation)
+    if lo < 1:
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_conv1d")
+    y = _out(y, (b, cout, lo), x)
+    _check(lib().sws_conv1d(x.data_ptr(), wgt.data_ptr(), y.data_ptr(), b, cin, length, cout, k, stride,
+                            pad, dilation, groups, _stream(stream)), "sws_conv1d")
+    return y
+
+
+def sws_conv2d(x, wgt, sh=1, sw=1, ph=0, pw=0, y=None, stream=None):
+    """x [N, Cin, H, W], wgt [Cout, Cin, kh, kw] -> y [N, Cout, Ho, Wo]."""
+    _dev(x, "x")
+    _dev(wgt, "wgt")
+    n, cin, h, wd = x.shape
+    cout, cin2, kh, kw = wgt.shape
+    if cin2 != cin:
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_conv2d")
+    ho, wo = sws_out_len(h, kh, sh, ph), sws_out_len(wd, kw, sw, pw)
+    if ho < 1 or wo < 1:
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_conv2d")
+    y = _out(y, (n, cout, ho, wo), x)
+    _check(lib().sws_conv2d(x.data_ptr(), wgt.data_ptr(), y.data_ptr(), n, cin, h, wd, cout, kh, kw,
+                            sh, sw, ph, pw, _stream(stream)), "sws_conv2d")
+    return y
+
+
+def sws_copy(src, dst=None, stream=None):
+    _dev(src, "src")
+    dst = _out(dst, tuple(src.shape), src, "dst")
+    _check(lib().sws_copy(src.data_ptr(), dst.data_ptr(), src.numel(), _stream(stream)), "sws_copy")
+    return dst

@@ -1,0 +1,342 @@
+// sws_slide1d — sliding window sums over rows (Section 2.2, Eq. 3) for gfx950.
+//
+// Two tuned kernels plus the direct-evaluation fallback:
+//
+//  * slide_direct_kernel (small windows): the Vector Slide idea of Section 3 (Algorithm 4)
+//    — the output vector is the (+) of w shifted copies of the input vector.  A lane owns
+//    four consecutive outputs and reads its shifted operands as 128-bit loads at +4, +8
+//    elements, which hit the same cache lines its neighbours fetch.
+//
+//  * slide_scan_kernel (large windows): the block form of the Vector Input algorithm
+//    (Section 3, Algorithm 2).  A wavefront owns a tile of 64*C consecutive inputs cut
+//    into segments of length S = w-1 (counted from the tile origin).  It builds
+//       Pre[q] = x[seg_start(q)] (+) ... (+) x[q]      (in-segment prefix sums, "X1")
+//       Suf[q] = x[q] (+) ... (+) x[seg_end(q)]        (in-segment suffix sums, "Y1")
+//    and every output costs ONE more (+):  y[q] = Suf[q] (+) Pre[q+S]  (older operand on
+//    the left), which holds exactly w terms because q and q+S sit at the same offset of
+//    adjacent segments.  Each lane scans C consecutive elements sequentially; the lane
+//    totals are combined by O(log(S/C)) cross-lane steps, so the work per output does not
+//    grow with w.  Global memory is touched only with fully coalesced 128-bit accesses
+//    (lane l <-> bytes 16*l of each 1 KB strip); LDS does the strip <-> chunk transposes.
+#include "sws_internal.h"
+
+namespace sws {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWavesPerWg = kThreads / kWave;
+
+__device__ __forceinline__ float lane_read(float v, int src_lane)
+{
+    return __int_as_float(__builtin_amdgcn_ds_bpermute((src_lane & 63) << 2, __float_as_int(v)));
+}
+
+// Orders the LDS traffic of one wavefront: everything written before is visible to the
+// lanes reading after.  No workgroup barrier — each wavefront owns its LDS slice.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+struct TilePlan {
+    int tiles_per_row;     // wave tiles along one row
+    int tout;              // outputs per wave tile
+    int group;             // consecutive tiles of a row handled by one workgroup
+    int chunks_per_row;    // workgroups per row
+    int64_t n_units;       // rows * chunks_per_row
+};
+
+TilePlan plan_tiles(int64_t rows, int lo, int max_tout)
+{
+    TilePlan p;
+    p.tiles_per_row = (lo + max_tout - 1) / max_tout;
+    p.tout = (lo + p.tiles_per_row - 1) / p.tiles_per_row;
+    const int64_t total = rows * p.tiles_per_row;
+    int64_t g = total / 2048;                      // aim for >= 8 workgroups per CU ...
+    if (g < kWavesPerWg) g = kWavesPerWg;          // ... but at least one tile per wavefront
+    if (g > p.tiles_per_row) g = p.tiles_per_row;
+    p.group = (int)g;
+    p.chunks_per_row = (p.tiles_per_row + p.group - 1) / p.group;
+    p.n_units = rows * p.chunks_per_row;
+    return p;
+}
+
+// ------------------------------------------------------------------------------------------
+// Small windows: y[i] = x[i] (+) x[i+1] (+) ... (+) x[i+W-1] from shifted 128-bit loads.
+// ------------------------------------------------------------------------------------------
+template <int OP, int W>
+__global__ __launch_bounds__(kThreads) void slide_direct_kernel(const float *__restrict__ x,
+                                                                float *__restrict__ y, int len, int lo,
+                                                                float scale, int tiles_per_row, int group,
+                                                                int chunks_per_row, int64_t n_units)
+{
+    using O = Op<OP>;
+    constexpr int NV = (W + 2) / 4 + 1;            // float4 groups covering x[q .. q+W+2]
+    const int64_t unit = xcd_unit(n_units);
+    if (unit < 0) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t r = unit / chunks_per_row;
+    const int chunk = (int)(unit - r * chunks_per_row);
+    const float *xr = x + r * (int64_t)len;
+    float *yr = y + r * (int64_t)lo;
+    int t_end = (chunk + 1) * group;
+    if (t_end > tiles_per_row) t_end = tiles_per_row;
+
+    for (int t = chunk * group + wave; t < t_end; t += kWavesPerWg) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int q = t * 1024 + j * 256 + 4 * lane;     // first of this lane's four outputs
+            if (q >= lo) continue;
+            float a[4 * NV];
+            if (q <= len - 4 * NV) {
+#pragma unroll
+                for (int u = 0; u < NV; ++u) {
+                    const v4f g = *(const v4f_u *)(xr + q + 4 * u);
+                    a[4 * u] = g.x; a[4 * u + 1] = g.y; a[4 * u + 2] = g.z; a[4 * u + 3] = g.w;
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < 4 * NV; ++u) a[u] = (q + u < len) ? xr[q + u] : O::id();
+            }
+            float o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float acc = a[e];
+#pragma unroll
+                for (int s = 1; s < W; ++s) acc = O::f(acc, a[e + s]);
+                o[e] = (OP == SWS_OP_ADD) ? acc * scale : acc;
+            }
+            if (q + 4 <= lo) {
+                const v4f g = {o[0], o[1], o[2], o[3]};
+                __builtin_nontemporal_store(g, (v4f_u *)(yr + q));
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (q + e < lo) yr[q + e] = o[e];
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Large windows: in-segment prefix + suffix sums, one (+) per output.
+// ------------------------------------------------------------------------------------------
+// LDS layout of one wave tile: local position q lives at q + 4*(q/16).  The 4-float pad
+// after every 16 floats makes both access shapes cheap: strips (lane l <-> q = 4*l) and
+// chunks (lane l <-> q = C*l .. C*l+C-1) are 16-byte aligned and spread over the banks.
+__device__ __forceinline__ int lds_pos(int q) { return q + ((q >> 4) << 2); }
+
+template <int OP, int C>
+__global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__restrict__ x,
+                                                              float *__restrict__ y, int len, int lo, int S,
+                                                              float scale, int tiles_per_row, int tout,
+                                                              int group, int chunks_per_row,
+                                                              int64_t n_units)
+{
+    using O = Op<OP>;
+    static_assert(C == 16, "the LDS layout assumes 16-element chunks");
+    constexpr int N = kWave * C;                    // inputs per wave tile
+    constexpr int NS = C / 4;                       // 256-element strips per tile
+    constexpr int REGION = N + N / 4;               // padded floats per LDS array
+    __shared__ __attribute__((aligned(16))) float lds[kWavesPerWg * 2 * REGION];
+
+    const int64_t unit = xcd_unit(n_units);
+    if (unit < 0) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float *A = lds + wave * 2 * REGION;             // staged inputs, later Pre
+    float *Bf = A + REGION;                         // Suf
+    const int64_t r = unit / chunks_per_row;
+    const int chunk = (int)(unit - r * chunks_per_row);
+    const float *xr = x + r * (int64_t)len;
+    float *yr = y + r * (int64_t)lo;
+    int t_end = (chunk + 1) * group;
+    if (t_end > tiles_per_row) t_end = tiles_per_row;
+
+    // Lane constants.  This lane scans local positions C*lane .. C*lane+C-1; isb[k] says a
+    // segment starts at element k (k = C: at the first element of the next lane).
+    const int q0 = (C * lane) % S;
+    bool isb[C + 1];
+    {
+        int q = q0;
+#pragma unroll
+        for (int k = 0; k <= C; ++k) {
+            isb[k] = (q == 0);
+            q = (q + 1 == S) ? 0 : q + 1;
+        }
+    }
+    const int n_pre = (q0 + C - 1) / C;             // earlier lanes holding part of my first segment
+    const int rem = (S - (q0 + C) % S) % S;         // elements of my last segment beyond my chunk
+    const int n_suf = (rem + C - 1) / C;            // later lanes holding them
+    const int max_reach = (S - 1 + C - 1) / C;
+    const int sh = S & 3;                           // misalignment of Pre[q+S] against strips
+
+    for (int t = chunk * group + wave; t < t_end; t += kWavesPerWg) {
+        const int t0 = t * tout;
+        // ---- stage the tile: coalesced strips -> LDS
+        if (t0 <= len - N) {
+#pragma unroll
+            for (int j = 0; j < NS; ++j) {
+                const int q = j * 256 + 4 * lane;
+                const v4f g = __builtin_nontemporal_load((const v4f_u *)(xr + t0 + q));
+                *(v4f *)(A + lds_pos(q)) = g;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < NS; ++j) {
+                const int q = j * 256 + 4 * lane;
+                v4f g;
+                g.x = (t0 + q + 0 < len) ? xr[t0 + q + 0] : O::id();
+                g.y = (t0 + q + 1 < len) ? xr[t0 + q + 1] : O::id();
+                g.z = (t0 + q + 2 < len) ? xr[t0 + q + 2] : O::id();
+                g.w = (t0 + q + 3 < len) ? xr[t0 + q + 3] : O::id();
+                *(v4f *)(A + lds_pos(q)) = g;
+            }
+        }
+        wave_lds_sync();
+        // ---- my chunk of C consecutive elements
+        float v[C];
+#pragma unroll
+        for (int u = 0; u < NS; ++u) {
+            const v4f g = *(const v4f *)(A + lds_pos(C * lane) + 4 * u);
+            v[4 * u] = g.x; v[4 * u + 1] = g.y; v[4 * u + 2] = g.z; v[4 * u + 3] = g.w;
+        }
+        // ---- pass 1: lane totals.  tail = my last segment's part inside the chunk,
+        //      head = my first segment's part inside the chunk.
+        float tail, head;
+        {
+            float p[C];
+            p[0] = v[0];
+#pragma unroll
+            for (int k = 1; k < C; ++k) p[k] = isb[k] ? v[k] : O::f(p[k - 1], v[k]);
+            tail = p[C - 1];
+            head = p[C - 1];
+#pragma unroll
+            for (int k = C - 2; k >= 0; --k) head = isb[k + 1] ? p[k] : head;
+        }
+        // ---- cross-lane: e = (+) of the tails of the n_pre lanes before me,
+        //                  g = (+) of the heads of the n_suf lanes after me.
+        float e = lane_read(tail, lane - 1);
+        float g = lane_read(head, lane + 1);
+        for (int d = 1; d < max_reach; d <<= 1) {
+            const float te = lane_read(e, lane - d);
+            const float tg = lane_read(g, lane + d);
+            if (n_pre > d) e = O::f(te, e);
+            if (n_suf > d) g = O::f(g, tg);
+        }
+        // ---- pass 2: seeded scans give the final in-segment prefix and suffix sums
+        float pre[C], suf[C];
+        pre[0] = isb[0] ? v[0] : O::f(e, v[0]);
+#pragma unroll
+        for (int k = 1; k < C; ++k) pre[k] = isb[k] ? v[k] : O::f(pre[k - 1], v[k]);
+        suf[C - 1] = isb[C] ? v[C - 1] : O::f(v[C - 1], g);
+#pragma unroll
+        for (int k = C - 2; k >= 0; --k) suf[k] = isb[k + 1] ? v[k] : O::f(v[k], suf[k + 1]);
+        // ---- chunks -> LDS (Pre over the staged inputs, Suf beside it)
+#pragma unroll
+        for (int u = 0; u < NS; ++u) {
+            const v4f gp = {pre[4 * u], pre[4 * u + 1], pre[4 * u + 2], pre[4 * u + 3]};
+            const v4f gs = {suf[4 * u], suf[4 * u + 1], suf[4 * u + 2], suf[4 * u + 3]};
+            *(v4f *)(A + lds_pos(C * lane) + 4 * u) = gp;
+            *(v4f *)(Bf + lds_pos(C * lane) + 4 * u) = gs;
+        }
+        wave_lds_sync();
+        // ---- combine on strips: y[q] = Suf[q] (+) Pre[q+S], then coalesced stores
+        int lim = lo - t0;
+        if (lim > tout) lim = tout;
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            const int q = j * 256 + 4 * lane;
+            if (q >= lim) continue;
+            const v4f s4 = *(const v4f *)(Bf + lds_pos(q));
+            const int a = q + S - sh;                            // aligned group holding Pre[q+S]
+            const v4f p0 = *(const v4f *)(A + lds_pos(a));
+            const v4f p1 = *(const v4f *)(A + lds_pos(a + 4));
+            v4f pn;
+            switch (sh) {
+            case 0: pn = p0; break;
+            case 1: pn = (v4f){p0.y, p0.z, p0.w, p1.x}; break;
+            case 2: pn = (v4f){p0.z, p0.w, p1.x, p1.y}; break;
+            default: pn = (v4f){p0.w, p1.x, p1.y, p1.z}; break;
+            }
+            v4f o;
+            o.x = O::f(s4.x, pn.x); o.y = O::f(s4.y, pn.y); o.z = O::f(s4.z, pn.z); o.w = O::f(s4.w, pn.w);
+            if (OP == SWS_OP_ADD) o *= scale;
+            if (q + 4 <= lim) {
+                __builtin_nontemporal_store(o, (v4f_u *)(yr + t0 + q));
+            } else {
+                if (q + 0 < lim) yr[t0 + q + 0] = o.x;
+                if (q + 1 < lim) yr[t0 + q + 1] = o.y;
+                if (q + 2 < lim) yr[t0 + q + 2] = o.z;
+            }
+        }
+        wave_lds_sync();                                         // the next tile overwrites A
+    }
+}
+
+template <int OP>
+hipError_t launch_direct(const float *x, float *y, int64_t rows, int len, int lo, int w, float scale,
+                         hipStream_t s)
+{
+    const TilePlan p = plan_tiles(rows, lo, 1024);
+    const int64_t grid = xcd_grid(p.n_units);
+    if (grid > 2147483647LL) return hipErrorInvalidValue;
+#define SWS_DIRECT(WV)                                                                                     \
+    case WV:                                                                                               \
+        hipLaunchKernelGGL((slide_direct_kernel<OP, WV>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, \
+                           len, lo, scale, p.tiles_per_row, p.group, p.chunks_per_row, p.n_units);         \
+        break
+    switch (w) {
+        SWS_DIRECT(1); SWS_DIRECT(2); SWS_DIRECT(3); SWS_DIRECT(4); SWS_DIRECT(5);
+        SWS_DIRECT(6); SWS_DIRECT(7); SWS_DIRECT(8); SWS_DIRECT(9);
+    default: return hipErrorInvalidValue;
+    }
+#undef SWS_DIRECT
+    return hipGetLastError();
+}
+
+template <int OP>
+hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, int w, float scale,
+                       hipStream_t s)
+{
+    constexpr int C = 16, N = kWave * C;
+    const int S = w - 1;
+    const TilePlan p = plan_tiles(rows, lo, N - S);
+    const int64_t grid = xcd_grid(p.n_units);
+    if (grid > 2147483647LL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((slide_scan_kernel<OP, C>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
+                       S, scale, p.tiles_per_row, p.tout, p.group, p.chunks_per_row, p.n_units);
+    return hipGetLastError();
+}
+
+constexpr int kDirectMaxW = 9;
+constexpr int kScanMaxW = kWave * 16 - 64 + 1;      // leaves at least 64 outputs per wave tile
+
+}  // namespace
+
+hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_t len64, int32_t w,
+                          float scale, hipStream_t s)
+{
+    const int len = (int)len64, lo = (int)(len64 - w + 1);
+    int variant = g_opt.slide_variant;
+    if (variant == 2 && w > kDirectMaxW) variant = 0;
+    if (variant == 3 && (w < 2 || w > kScanMaxW)) variant = 0;
+    if (variant == 0) variant = (w <= 8) ? 2 : (w <= kScanMaxW ? 3 : 1);
+    if (variant == 1) return launch_slide1d_naive(op, x, y, rows, len64, w, scale, s);
+    if (variant == 2) {
+        switch (op) {
+        case SWS_OP_ADD: return launch_direct<SWS_OP_ADD>(x, y, rows, len, lo, w, scale, s);
+        case SWS_OP_MAX: return launch_direct<SWS_OP_MAX>(x, y, rows, len, lo, w, scale, s);
+        default: return launch_direct<SWS_OP_MIN>(x, y, rows, len, lo, w, scale, s);
+        }
+    }
+    switch (op) {
+    case SWS_OP_ADD: return launch_scan<SWS_OP_ADD>(x, y, rows, len, lo, w, scale, s);
+    case SWS_OP_MAX: return launch_scan<SWS_OP_MAX>(x, y, rows, len, lo, w, scale, s);
+    default: return launch_scan<SWS_OP_MIN>(x, y, rows, len, lo, w, scale, s);
+    }
+}
+
+}  // namespace sws

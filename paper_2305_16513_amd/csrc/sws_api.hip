@@ -1,0 +1,146 @@
+// C ABI of libsws: argument checks and dispatch.  Nothing here touches device data.
+#include <string.h>
+
+#include "sws_internal.h"
+
+namespace sws {
+Options g_opt = {0, 0, 0, 0, 0, 0};
+}
+
+namespace {
+
+constexpr int64_t kMaxDim = 2147483647LL - 65536;   // per-row / per-plane extents are indexed in int32
+                                                    // with headroom for one tile of look-ahead
+
+bool mul3(int64_t a, int64_t b, int64_t c, int64_t *out)
+{
+    int64_t t;
+    if (__builtin_mul_overflow(a, b, &t)) return false;
+    if (__builtin_mul_overflow(t, c, out)) return false;
+    return *out <= (INT64_MAX / 4);        // byte offsets must fit as well
+}
+
+bool valid_op(int op) { return op == SWS_OP_ADD || op == SWS_OP_MAX || op == SWS_OP_MIN; }
+
+sws_status from_hip(hipError_t e) { return e == hipSuccess ? SWS_OK : SWS_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char *sws_version(void) { return "0.1"; }
+
+const char *sws_status_string(int status)
+{
+    switch (status) {
+    case SWS_OK: return "ok";
+    case SWS_ERR_INVALID_ARG: return "invalid argument";
+    case SWS_ERR_UNSUPPORTED: return "unsupported configuration";
+    case SWS_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+int64_t sws_out_len(int64_t len, int32_t w, int32_t stride, int32_t pad, int32_t dilation)
+{
+    if (len < 0 || w < 1 || stride < 1 || pad < 0 || dilation < 1) return -1;
+    const int64_t span = (int64_t)dilation * (w - 1) + 1;
+    const int64_t padded = len + 2 * (int64_t)pad;
+    if (span > padded) return -1;
+    return (padded - span) / stride + 1;
+}
+
+sws_status sws_set_option(const char *key, int64_t value)
+{
+    if (!key) return SWS_ERR_INVALID_ARG;
+    const int v = (int)value;
+    if (!strcmp(key, "slide_variant")) sws::g_opt.slide_variant = v;
+    else if (!strcmp(key, "slide_chunk")) sws::g_opt.slide_chunk = v;
+    else if (!strcmp(key, "pool2d_variant")) sws::g_opt.pool2d_variant = v;
+    else if (!strcmp(key, "conv1d_variant")) sws::g_opt.conv1d_variant = v;
+    else if (!strcmp(key, "conv2d_variant")) sws::g_opt.conv2d_variant = v;
+    else if (!strcmp(key, "copy_variant")) sws::g_opt.copy_variant = v;
+    else return SWS_ERR_INVALID_ARG;
+    return SWS_OK;
+}
+
+sws_status sws_copy(const float *src, float *dst, int64_t n, void *stream)
+{
+    if (n < 0 || n > INT64_MAX / 4) return SWS_ERR_INVALID_ARG;
+    if (n == 0) return SWS_OK;
+    if (!src || !dst) return SWS_ERR_INVALID_ARG;
+    return from_hip(sws::launch_copy(src, dst, n, (hipStream_t)stream));
+}
+
+sws_status sws_slide1d(sws_op op, const float *x, float *y, int64_t rows, int64_t len, int32_t w,
+                       float scale, void *stream)
+{
+    if (!valid_op((int)op) || rows < 0 || len < 0 || w < 1) return SWS_ERR_INVALID_ARG;
+    if (len > kMaxDim || (int64_t)w > len) return SWS_ERR_INVALID_ARG;
+    int64_t n_in;
+    if (!mul3(rows, len, 1, &n_in)) return SWS_ERR_INVALID_ARG;
+    if (rows == 0) return SWS_OK;
+    if (!x || !y) return SWS_ERR_INVALID_ARG;
+    return from_hip(sws::launch_slide1d((int)op, x, y, rows, len, w, scale, (hipStream_t)stream));
+}
+
+sws_status sws_pool2d(sws_op op, const float *x, float *y, int64_t N, int64_t C, int64_t H, int64_t W,
+                      int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
+                      float scale, void *stream)
+{
+    if (!valid_op((int)op) || N < 0 || C < 0 || H < 0 || W < 0) return SWS_ERR_INVALID_ARG;
+    if (kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0) return SWS_ERR_INVALID_ARG;
+    if (ph >= kh || pw >= kw) return SWS_ERR_INVALID_ARG;
+    if (H > kMaxDim || W > kMaxDim) return SWS_ERR_INVALID_ARG;
+    const int64_t Ho = sws_out_len(H, kh, sh, ph, 1), Wo = sws_out_len(W, kw, sw, pw, 1);
+    if (Ho < 1 || Wo < 1) return SWS_ERR_INVALID_ARG;
+    int64_t planes, n_in, n_out;
+    if (!mul3(N, C, 1, &planes) || !mul3(planes, H, W, &n_in) || !mul3(planes, Ho, Wo, &n_out))
+        return SWS_ERR_INVALID_ARG;
+    if (H * W > kMaxDim) return SWS_ERR_UNSUPPORTED;
+    if (planes == 0) return SWS_OK;
+    if (!x || !y) return SWS_ERR_INVALID_ARG;
+    return from_hip(sws::launch_pool2d((int)op, x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale,
+                                       (hipStream_t)stream));
+}
+
+sws_status sws_conv1d(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin, int64_t L,
+                      int64_t Cout, int32_t k, int32_t stride, int32_t pad, int32_t dilation,
+                      int32_t groups, void *stream)
+{
+    if (B < 0 || Cin < 1 || L < 0 || Cout < 1 || k < 1 || stride < 1 || pad < 0 || dilation < 1 || groups < 1)
+        return SWS_ERR_INVALID_ARG;
+    if (Cin % groups || Cout % groups || L > kMaxDim || Cin > kMaxDim || Cout > kMaxDim)
+        return SWS_ERR_INVALID_ARG;
+    const int64_t Lo = sws_out_len(L, k, stride, pad, dilation);
+    if (Lo < 1) return SWS_ERR_INVALID_ARG;
+    int64_t n_in, n_out, n_w;
+    if (!mul3(B, Cin, L, &n_in) || !mul3(B, Cout, Lo, &n_out) || !mul3(Cout, Cin / groups, k, &n_w))
+        return SWS_ERR_INVALID_ARG;
+    if (B == 0) return SWS_OK;
+    if (!x || !wgt || !y) return SWS_ERR_INVALID_ARG;
+    return from_hip(sws::launch_conv1d(x, wgt, y, B, Cin, L, Cout, Lo, k, stride, pad, dilation, groups,
+                                       (hipStream_t)stream));
+}
+
+sws_status sws_conv2d(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
+                      int64_t W, int64_t Cout, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph,
+                      int32_t pw, void *stream)
+{
+    if (N < 0 || Cin < 1 || H < 0 || W < 0 || Cout < 1) return SWS_ERR_INVALID_ARG;
+    if (kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0) return SWS_ERR_INVALID_ARG;
+    if (H > kMaxDim || W > kMaxDim || Cin > kMaxDim || Cout > kMaxDim) return SWS_ERR_INVALID_ARG;
+    const int64_t Ho = sws_out_len(H, kh, sh, ph, 1), Wo = sws_out_len(W, kw, sw, pw, 1);
+    if (Ho < 1 || Wo < 1) return SWS_ERR_INVALID_ARG;
+    int64_t t, n_in, n_out, n_w;
+    if (!mul3(N, Cin, H, &t) || !mul3(t, W, 1, &n_in)) return SWS_ERR_INVALID_ARG;
+    if (!mul3(N, Cout, Ho, &t) || !mul3(t, Wo, 1, &n_out)) return SWS_ERR_INVALID_ARG;
+    if (!mul3(Cout, Cin, (int64_t)kh * kw, &n_w)) return SWS_ERR_INVALID_ARG;
+    if (H * W > kMaxDim || Ho * Wo > kMaxDim || n_w > kMaxDim) return SWS_ERR_UNSUPPORTED;
+    if (N == 0) return SWS_OK;
+    if (!x || !wgt || !y) return SWS_ERR_INVALID_ARG;
+    return from_hip(sws::launch_conv2d(x, wgt, y, N, Cin, H, W, Cout, Ho, Wo, kh, kw, sh, sw, ph, pw,
+                                       (hipStream_t)stream));
+}
+
+}  // extern "C"

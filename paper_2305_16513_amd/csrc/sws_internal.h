@@ -1,0 +1,82 @@
+// Internal declarations shared by the libsws translation units (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sws.h"
+
+namespace sws {
+
+// Developer knobs set through sws_set_option(); 0 means "choose automatically".
+struct Options {
+    int slide_variant;
+    int slide_chunk;
+    int pool2d_variant;
+    int conv1d_variant;
+    int conv2d_variant;
+    int copy_variant;
+};
+extern Options g_opt;
+
+constexpr int kWave = 64;    // CDNA wavefront width
+constexpr int kXcd = 8;      // XCDs (separate L2s) on MI355X
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef v4f v4f_u __attribute__((aligned(4)));     // 16-byte access at 4-byte alignment
+typedef float v2f __attribute__((ext_vector_type(2)));
+
+// The operator (+) of the sliding window sum, with its identity element.  `a` is always
+// the older (left) operand so the kernels stay valid for non-commutative operators.
+template <int OP> struct Op;
+template <> struct Op<SWS_OP_ADD> {
+    static __device__ __forceinline__ float id() { return 0.0f; }
+    static __device__ __forceinline__ float f(float a, float b) { return a + b; }
+};
+template <> struct Op<SWS_OP_MAX> {
+    static __device__ __forceinline__ float id() { return -__builtin_huge_valf(); }
+    static __device__ __forceinline__ float f(float a, float b) { return a < b ? b : a; }
+};
+template <> struct Op<SWS_OP_MIN> {
+    static __device__ __forceinline__ float id() { return __builtin_huge_valf(); }
+    static __device__ __forceinline__ float f(float a, float b) { return b < a ? b : a; }
+};
+
+// Workgroups are dealt round-robin to the 8 XCDs.  This maps blockIdx so that each XCD
+// (one L2) walks a contiguous range of work units, keeping a tile's halo re-read in the
+// L2 that fetched it.  Returns an id in [0, n_units) or -1 for the padding blocks.
+__device__ __forceinline__ int64_t xcd_unit(int64_t n_units)
+{
+    const int64_t b = blockIdx.x;
+    const int64_t per = (n_units + kXcd - 1) / kXcd;
+    const int64_t u = (b % kXcd) * per + b / kXcd;
+    return (b / kXcd < per && u < n_units) ? u : -1;
+}
+inline int64_t xcd_grid(int64_t n_units) { return ((n_units + kXcd - 1) / kXcd) * kXcd; }
+
+hipError_t launch_copy(const float *src, float *dst, int64_t n, hipStream_t s);
+hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_t len, int32_t w,
+                          float scale, hipStream_t s);
+hipError_t launch_pool2d(int op, const float *x, float *y, int64_t planes, int64_t H, int64_t W,
+                         int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                         int32_t ph, int32_t pw, float scale, hipStream_t s);
+hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin, int64_t L,
+                         int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad,
+                         int32_t dilation, int32_t groups, hipStream_t s);
+hipError_t launch_conv2d(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
+                         int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw,
+                         int32_t sh, int32_t sw, int32_t ph, int32_t pw, hipStream_t s);
+
+// Direct-evaluation fallbacks (naive_kernels.hip).
+hipError_t launch_slide1d_naive(int op, const float *x, float *y, int64_t rows, int64_t len, int32_t w,
+                                float scale, hipStream_t s);
+hipError_t launch_pool2d_naive(int op, const float *x, float *y, int64_t planes, int64_t H, int64_t W,
+                               int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                               int32_t ph, int32_t pw, float scale, hipStream_t s);
+hipError_t launch_conv1d_naive(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin,
+                               int64_t L, int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad,
+                               int32_t dilation, int32_t groups, hipStream_t s);
+hipError_t launch_conv2d_naive(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin,
+                               int64_t H, int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh,
+                               int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw, hipStream_t s);
+
+}  // namespace sws

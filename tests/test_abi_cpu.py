@@ -1,0 +1,123 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "sws.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2305_16513_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2305_16513_amd import build
+        build.build()
+    return binding.lib()
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sws_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(L):
+    from paper_2305_16513_amd import binding
+    names = _declared()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_out_len(L):
+    assert L.sws_out_len(1048576, 5, 1, 0, 1) == 1048572
+    assert L.sws_out_len(4096, 3, 1, 0, 1) == 4094
+    assert L.sws_out_len(112, 3, 2, 1, 1) == 56
+    assert L.sws_out_len(112, 3, 1, 1, 1) == 112
+    assert L.sws_out_len(16384, 255, 1, 0, 1) == 16130
+    assert L.sws_out_len(10, 3, 1, 0, 4) == 2
+    assert L.sws_out_len(4, 5, 1, 0, 1) == -1
+    assert L.sws_out_len(4, 0, 1, 0, 1) == -1
+    assert L.sws_out_len(4, 2, 0, 0, 1) == -1
+    assert L.sws_out_len(-1, 2, 1, 0, 1) == -1
+
+
+def test_status_strings(L):
+    seen = {L.sws_status_string(i) for i in range(4)}
+    assert len(seen) == 4 and all(s for s in seen)
+    assert L.sws_status_string(99)
+
+
+def test_slide1d_argument_checks(L):
+    one = ctypes.c_void_p(16)      # never dereferenced: every call below fails or is empty
+    nul = ctypes.c_void_p(0)
+    assert L.sws_slide1d(0, one, one, 0, 100, 3, 1.0, nul) == 0            # no rows: nothing to do
+    assert L.sws_slide1d(7, one, one, 1, 100, 3, 1.0, nul) == 1            # unknown op
+    assert L.sws_slide1d(0, one, one, 1, 100, 0, 1.0, nul) == 1            # w < 1
+    assert L.sws_slide1d(0, one, one, 1, 100, 101, 1.0, nul) == 1          # w > len
+    assert L.sws_slide1d(0, one, one, -1, 100, 3, 1.0, nul) == 1
+    assert L.sws_slide1d(0, one, one, 1, -5, 3, 1.0, nul) == 1
+    assert L.sws_slide1d(0, nul, one, 1, 100, 3, 1.0, nul) == 1            # NULL with output
+    assert L.sws_slide1d(0, one, nul, 1, 100, 3, 1.0, nul) == 1
+    assert L.sws_slide1d(0, one, one, 1, 2 ** 31, 3, 1.0, nul) == 1        # row too long for int32
+    assert L.sws_slide1d(0, one, one, 2 ** 40, 2 ** 30, 3, 1.0, nul) == 1  # size overflow
+
+
+def test_pool2d_argument_checks(L):
+    one, nul = ctypes.c_void_p(16), ctypes.c_void_p(0)
+    ok = (0, one, one, 0, 3, 8, 8, 3, 3, 1, 1, 1, 1, 1.0, nul)
+    assert L.sws_pool2d(*ok) == 0                                          # N = 0
+    bad = lambda **kw: L.sws_pool2d(*[kw.get(n, v) for n, v in zip(
+        ("op", "x", "y", "N", "C", "H", "W", "kh", "kw", "sh", "sw", "ph", "pw", "scale", "s"),
+        (0, one, one, 1, 3, 8, 8, 3, 3, 1, 1, 1, 1, 1.0, nul))])
+    assert bad(op=5) == 1
+    assert bad(kh=0) == 1
+    assert bad(sw=0) == 1
+    assert bad(ph=3) == 1                                                  # window wholly in padding
+    assert bad(pw=-1) == 1
+    assert bad(kh=11) == 1                                                 # window larger than padded input
+    assert bad(x=nul) == 1
+    assert bad(N=-1) == 1
+
+
+def test_conv_argument_checks(L):
+    one, nul = ctypes.c_void_p(16), ctypes.c_void_p(0)
+    c1 = lambda **kw: L.sws_conv1d(*[kw.get(n, v) for n, v in zip(
+        ("x", "w", "y", "B", "Cin", "L", "Cout", "k", "stride", "pad", "dil", "groups", "s"),
+        (one, one, one, 1, 4, 32, 6, 3, 1, 0, 1, 1, nul))])
+    assert c1(B=0) == 0
+    assert c1(groups=3) == 1                                               # Cin % groups
+    assert c1(groups=4) == 1                                               # Cout % groups
+    assert c1(k=0) == 1 and c1(stride=0) == 1 and c1(dil=0) == 1 and c1(pad=-1) == 1
+    assert c1(k=33) == 1                                                   # taps span more than the row
+    assert c1(k=9, dil=4) == 1
+    assert c1(w=nul) == 1 and c1(x=nul) == 1 and c1(y=nul) == 1
+    c2 = lambda **kw: L.sws_conv2d(*[kw.get(n, v) for n, v in zip(
+        ("x", "w", "y", "N", "Cin", "H", "W", "Cout", "kh", "kw", "sh", "sw", "ph", "pw", "s"),
+        (one, one, one, 1, 4, 8, 8, 6, 3, 3, 1, 1, 1, 1, nul))])
+    assert c2(N=0) == 0
+    assert c2(kh=0) == 1 and c2(sw=0) == 1 and c2(ph=-1) == 1 and c2(Cin=0) == 1
+    assert c2(kw=11) == 1
+    assert c2(w=nul) == 1
+
+
+def test_options_and_copy_checks(L):
+    assert L.sws_set_option(b"slide_variant", 0) == 0
+    assert L.sws_set_option(b"no_such_knob", 1) == 1
+    assert L.sws_set_option(None, 1) == 1
+    one, nul = ctypes.c_void_p(16), ctypes.c_void_p(0)
+    assert L.sws_copy(one, one, 0, nul) == 0
+    assert L.sws_copy(one, one, -1, nul) == 1
+    assert L.sws_copy(nul, one, 8, nul) == 1
+
+
+def test_binding_refuses_cpu_tensors():
+    """The product path never computes on the CPU: host tensors are an error."""
+    import torch
+    from paper_2305_16513_amd import binding
+    with pytest.raises(TypeError):
+        binding.sws_slide1d(0, torch.zeros(8), 3)

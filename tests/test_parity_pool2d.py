@@ -1,0 +1,95 @@
+"""GPU parity of sws_pool2d against the CPU oracle (Section 2.3 in two dimensions)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2305_16513_amd import workloads
+from parity_util import assert_bit_exact, assert_within_tol, to_gpu, to_host
+
+pytestmark = pytest.mark.gpu
+OPS = {"add": 0, "max": 1, "min": 2}
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2305_16513_amd import binding
+    binding.lib()
+    yield binding
+    binding.sws_set_option("pool2d_variant", 0)
+
+
+def _check(B, op, x, kh, kw, sh, sw, ph, pw, what=""):
+    scale = 1.0 / (kh * kw)
+    y = to_host(B.sws_pool2d(OPS[op], to_gpu(x), kh, kw, sh, sw, ph, pw, scale))
+    ref, mag = oracle.pool2d(OPS[op], x, kh, kw, sh, sw, ph, pw, scale)
+    if op == "add":
+        return assert_within_tol(y, ref, mag, what)
+    assert_bit_exact(y, ref, what)
+    return 0.0
+
+
+GEOMS = [
+    # kh kw sh sw ph pw
+    (3, 3, 1, 1, 1, 1), (3, 3, 2, 2, 1, 1), (3, 3, 1, 1, 0, 0), (2, 2, 2, 2, 0, 0), (5, 5, 1, 1, 2, 2),
+    (3, 5, 1, 2, 1, 2), (7, 2, 3, 1, 3, 0), (1, 1, 1, 1, 0, 0), (1, 4, 1, 1, 0, 3), (4, 1, 2, 1, 3, 0),
+    (13, 13, 1, 1, 6, 6), (3, 3, 3, 3, 0, 0),
+]
+
+
+@pytest.mark.parametrize("op", ["add", "max", "min"])
+@pytest.mark.parametrize("geom", GEOMS)
+@pytest.mark.parametrize("shape", [(2, 3, 37, 53), (1, 5, 112, 112), (3, 2, 16, 200), (2, 2, 129, 19)])
+def test_geometries(B, op, geom, shape):
+    kh, kw, sh, sw, ph, pw = geom
+    if kh > shape[2] + 2 * ph or kw > shape[3] + 2 * pw:
+        pytest.skip("window larger than plane")
+    rng = np.random.Generator(np.random.PCG64(hash((geom, shape)) % (2 ** 31)))
+    x = rng.standard_normal(shape, dtype=np.float32)
+    _check(B, op, x, *geom, what="%s %s %s" % (op, geom, shape))
+
+
+def test_all_negative_plane_max_ignores_padding(B):
+    x = -np.abs(np.random.Generator(np.random.PCG64(3)).standard_normal((2, 2, 20, 24), dtype=np.float32)) - 1
+    _check(B, "max", x, 3, 3, 1, 1, 1, 1)
+    _check(B, "min", -x, 3, 3, 2, 2, 1, 1)
+
+
+def test_add_bit_exact_on_integer_valued_input(B):
+    x = workloads.integer_valued((2, 3, 57, 61), -32, 32, seed=9)
+    y = to_host(B.sws_pool2d(0, to_gpu(x), 3, 3, 1, 1, 1, 1, 1.0))
+    ref, _ = oracle.pool2d(0, x, 3, 3, 1, 1, 1, 1, 1.0)
+    assert np.array_equal(y.astype(np.float64), ref)
+
+
+def test_tiny_planes(B):
+    for shape in [(1, 1, 1, 1), (3, 1, 2, 2), (1, 2, 3, 1), (2, 2, 1, 9)]:
+        x = np.random.Generator(np.random.PCG64(11)).standard_normal(shape, dtype=np.float32)
+        _check(B, "add", x, 1, 1, 1, 1, 0, 0)
+        if shape[2] >= 2 and shape[3] >= 2:
+            _check(B, "max", x, 2, 2, 1, 1, 1, 1)
+
+
+@pytest.mark.parametrize("stride", [1, 2])
+def test_cfg3_full_size_sampled_planes(B, stride):
+    """[32, 64, 112, 112], 3x3, pad 1, stride 1 and 2, at full size in one launch; the
+    oracle checks a seeded sample of whole planes plus the first and last plane, and a
+    size-independent property covers every output: max >= centre tap, and the stride-2
+    result is the stride-1 result subsampled."""
+    import torch
+    x, _ = workloads.make(3)
+    xg = to_gpu(x)
+    rng = np.random.Generator(np.random.PCG64(33 + stride))
+    planes = sorted(set([0, 2047] + rng.integers(0, 2048, size=30).tolist()))
+    xs = x.reshape(2048, 1, 112, 112)[planes]
+    for op in ("max", "add"):
+        yg = B.sws_pool2d(OPS[op], xg, 3, 3, stride, stride, 1, 1, 1.0 / 9)
+        y = to_host(yg).reshape(2048, 1, yg.shape[2], yg.shape[3])[planes]
+        ref, mag = oracle.pool2d(OPS[op], xs, 3, 3, stride, stride, 1, 1, 1.0 / 9)
+        if op == "max":
+            assert_bit_exact(y, ref, "cfg3 max s%d" % stride)
+            assert bool((yg >= xg[:, :, ::stride, ::stride]).all())
+        else:
+            assert_within_tol(y, ref, mag, "cfg3 avg s%d" % stride)
+        if stride == 2:
+            y1 = B.sws_pool2d(OPS[op], xg, 3, 3, 1, 1, 1, 1, 1.0 / 9)
+            assert torch.equal(yg, y1[:, :, ::2, ::2])

@@ -1,0 +1,139 @@
+"""GPU parity of sws_slide1d against the CPU oracle (Section 2.2, Eq. 3), through the C ABI.
+
+Sizes are chosen so that every kernel sees several tiles and a ragged tail; max / min must
+be bit-exact, add must satisfy |err| <= 1e-5 * sum|terms| per output."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2305_16513_amd import workloads
+from parity_util import assert_bit_exact, assert_within_tol, to_gpu, to_host
+
+pytestmark = pytest.mark.gpu
+
+OPS = {"add": 0, "max": 1, "min": 2}
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2305_16513_amd import binding
+    binding.lib()
+    yield binding
+    binding.sws_set_option("slide_variant", 0)
+
+
+def _check(B, op, x, w, scale=1.0, what=""):
+    y = to_host(B.sws_slide1d(OPS[op], to_gpu(x), w, scale))
+    ref, mag = oracle.slide1d(OPS[op], x.reshape(-1, x.shape[-1]), w, scale)
+    ref, mag = ref.reshape(y.shape), mag.reshape(y.shape)
+    if op == "add":
+        return assert_within_tol(y, ref, mag, what)
+    assert_bit_exact(y, ref, what)
+    return 0.0
+
+
+WINDOWS = [1, 2, 3, 4, 5, 7, 8, 9, 10, 15, 16, 17, 31, 33, 64, 65, 100, 255, 256, 257, 500, 770, 961]
+
+
+@pytest.mark.parametrize("op", ["add", "max", "min"])
+@pytest.mark.parametrize("w", WINDOWS)
+def test_several_tiles_and_ragged_tail(B, op, w):
+    """3 rows of 5003 (not a multiple of 4: every row after the first is misaligned)."""
+    rng = np.random.Generator(np.random.PCG64(1000 + w))
+    x = (rng.random((3, 5003), dtype=np.float32) * 2 - 1).astype(np.float32)
+    _check(B, op, x, w, scale=1.0 / w, what="%s w=%d" % (op, w))
+
+
+@pytest.mark.parametrize("op", ["add", "max"])
+@pytest.mark.parametrize("length,w", [(1, 1), (2, 2), (5, 5), (17, 16), (64, 9), (255, 255), (256, 255),
+                                      (1023, 300), (1024, 64), (1025, 2), (2047, 1000), (4097, 1025)])
+def test_degenerate_and_short_rows(B, op, length, w):
+    """Single-output rows, rows shorter than a tile, windows beyond the scan kernel's reach."""
+    rng = np.random.Generator(np.random.PCG64(length * 7 + w))
+    x = rng.standard_normal((5, length), dtype=np.float32)
+    _check(B, op, x, w, what="%s len=%d w=%d" % (op, length, w))
+
+
+@pytest.mark.parametrize("w", [3, 8, 9, 16, 64, 255])
+def test_add_is_bit_exact_on_integer_valued_input(B, w):
+    """Every fp32 partial sum is exact, so any association order must give the same bits."""
+    x = workloads.integer_valued((4, 3001), -64, 64, seed=w)
+    y = to_host(B.sws_slide1d(0, to_gpu(x), w))
+    ref, _ = oracle.slide1d(0, x, w)
+    assert np.array_equal(y.astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("variant", [1, 2, 3])
+@pytest.mark.parametrize("w", [2, 5, 9])
+def test_every_kernel_variant(B, variant, w):
+    rng = np.random.Generator(np.random.PCG64(variant * 100 + w))
+    x = rng.standard_normal((7, 2500), dtype=np.float32)
+    B.sws_set_option("slide_variant", variant)
+    try:
+        for op in ("add", "max", "min"):
+            _check(B, op, x, w, scale=0.25, what="variant %d %s w=%d" % (variant, op, w))
+    finally:
+        B.sws_set_option("slide_variant", 0)
+
+
+def test_many_short_rows(B):
+    """More rows than any grid dimension trick would hide: 40000 rows of 37."""
+    rng = np.random.Generator(np.random.PCG64(77))
+    x = rng.standard_normal((40000, 37), dtype=np.float32)
+    _check(B, "add", x, 5)
+    _check(B, "max", x, 12)
+
+
+def test_leading_dimensions_are_rows(B):
+    x, _ = workloads.make(2, x_shape=(2, 3, 300))
+    y = to_host(B.sws_slide1d(1, to_gpu(x), 3))
+    ref, _ = oracle.slide1d(1, x.reshape(6, 300), 3)
+    assert y.shape == (2, 3, 298)
+    assert_bit_exact(y.reshape(6, 298), ref)
+
+
+def test_scale_ignored_for_max(B):
+    x, _ = workloads.make(1, x_shape=(1, 1, 999))
+    a = to_host(B.sws_slide1d(1, to_gpu(x), 16, 123.0))
+    b = to_host(B.sws_slide1d(1, to_gpu(x), 16, 1.0))
+    assert np.array_equal(a, b)
+
+
+def test_poisoned_surroundings(B):
+    """x and y sit in the middle of larger device buffers filled with huge sentinels: a
+    read that strays outside x shows up in the result, a write outside y in the guard."""
+    import torch
+    rng = np.random.Generator(np.random.PCG64(5))
+    rows, length, guard = 6, 1501, 4099
+    x = rng.standard_normal((rows, length), dtype=np.float32)
+    for w in (1, 5, 64, 255, 1100):
+        lo = length - w + 1
+        for op in ("add", "max"):
+            xbuf = torch.full((guard + rows * length + guard,), 1e30, device="cuda")
+            ybuf = torch.full((guard + rows * lo + guard,), -7e29, device="cuda")
+            xin = xbuf[guard:guard + rows * length].view(rows, length)
+            xin.copy_(torch.from_numpy(x))
+            yout = ybuf[guard:guard + rows * lo].view(rows, lo)
+            B.sws_slide1d(OPS[op], xin, w, 1.0, y=yout)
+            ref, mag = oracle.slide1d(OPS[op], x, w)
+            if op == "add":
+                assert_within_tol(to_host(yout), ref, mag, "guarded add w=%d" % w)
+            else:
+                assert_bit_exact(to_host(yout), ref, "guarded max w=%d" % w)
+            assert bool((ybuf[:guard] == -7e29).all()) and bool((ybuf[guard + rows * lo:] == -7e29).all())
+
+
+def test_cfg1_full_size(B):
+    """1-D single sequence, N = 1,048,576, w = 5: sliding add and max at full size."""
+    x, _ = workloads.make(1)
+    workloads.check_clean(x)
+    worst = _check(B, "add", x.reshape(1, -1), 5, what="cfg1 add")
+    _check(B, "max", x.reshape(1, -1), 5, what="cfg1 max")
+    assert worst < 1e-6
+
+
+def test_cfg2_pooling_full_size(B):
+    """[16, 64, 4096] avg and max pool, w = 3, stride 1."""
+    x, _ = workloads.make(2)
+    _check(B, "add", x.reshape(-1, 4096), 3, scale=1.0 / 3, what="cfg2 avg")
+    _check(B, "max", x.reshape(-1, 4096), 3, what="cfg2 max")
