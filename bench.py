@@ -1,0 +1,278 @@
+#!/usr/bin/env python3
+"""Benchmark of the sliding-window-sum hot path on one MI355X.
+
+A "step" is one pass of the hot path over configuration 5 (the largest single-GPU
+workload, 2 GiB of input, genuinely HBM-cold): sliding add and sliding max with
+w in {16, 64, 255} over x[256,128,16384] plus the 31-tap depthwise convolution —
+seven launches through the C ABI.  Inputs are resident in HBM before the clock starts.
+
+    value    = algorithmic bytes of a step / wall time of a step            [GB/s]
+    roofline = the dominant kernel's algorithmic bytes per launch / its mean launch
+               duration (HIP events on the launch stream, inside the timed region),
+               against the 8 TB/s HBM peak
+    ops      = every operator of all five configurations timed on its own (pooling in
+               GB/s, convolution in GFLOP/s, each with its fraction of roofline)
+    cpu_baseline = the fp64 oracle on a bounded sample of the same workload
+
+Prints ONE JSON line on stdout.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+FP32_PEAK_GFLOPS = 157300.0
+ROWS5, LEN5, CH5, K5 = 256 * 128, 16384, 128, 31
+WINDOWS5 = (16, 64, 255)
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ops", action="store_true", help="skip the per-operator table of configs 1-4")
+    return ap.parse_args()
+
+
+def slide_bytes(rows, length, w):
+    return 4 * (rows * length + rows * (length - w + 1))
+
+
+def read_traffic(name):
+    """HBM bytes per launch measured offline with rocprofv3 counters (profiles/), or None."""
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def time_launches(torch, fn, iters, warm=2):
+    """Mean duration in ms of `fn` (one launch) from events on the current stream."""
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+    evs[0].record()
+    for i in range(iters):
+        fn()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    ts = [evs[i].elapsed_time(evs[i + 1]) for i in range(iters)]
+    return sum(ts) / len(ts)
+
+
+def ops_table(torch, B, workloads, iters=20):
+    """Each operator of configurations 1-4 on its own.  These tensors fit in the 256 MB
+    last-level cache, so besides the warm figure a cold one is taken by rotating through
+    enough distinct buffers that more than 512 MB is touched between reuses."""
+    out = {}
+
+    def rotate(make_args, nbytes):
+        n = max(1, min(64, int(600e6 // max(nbytes, 1)) + 1))
+        sets = [make_args() for _ in range(n)]
+        state = {"i": 0}
+
+        def pick():
+            state["i"] = (state["i"] + 1) % n
+            return sets[state["i"]]
+        return sets[0], pick
+
+    def record(name, launch, make_args, nbytes, flops=0.0):
+        first, pick = rotate(make_args, nbytes)
+        warm = time_launches(torch, lambda: launch(*first), iters)
+        cold = time_launches(torch, lambda: launch(*pick()), iters)
+        rec = {"ms_warm": round(warm, 5), "ms_cold": round(cold, 5),
+               "GBps_cold": round(nbytes / cold / 1e6, 1),
+               "frac_hbm_cold": round(nbytes / cold / 1e6 / HBM_PEAK_GBPS, 4)}
+        if flops:
+            rec["GFLOPs_warm"] = round(flops / warm / 1e6, 1)
+            rec["GFLOPs_cold"] = round(flops / cold / 1e6, 1)
+            rec["frac_fp32_peak_warm"] = round(flops / warm / 1e6 / FP32_PEAK_GFLOPS, 4)
+        out[name] = rec
+
+    g = lambda a: torch.from_numpy(a).cuda()
+    # cfg1: one sequence of 1,048,576, w = 5
+    x1, t1 = workloads.make(1)
+    x1, t1 = g(x1), g(t1)
+    mk = lambda: (x1.clone(), torch.empty(1, 1, 1048572, device="cuda"))
+    nb = slide_bytes(1, 1048576, 5)
+    record("cfg1_slide_add_w5", lambda x, y: B.sws_slide1d(0, x, 5, 0.2, y=y), mk, nb)
+    record("cfg1_slide_max_w5", lambda x, y: B.sws_slide1d(1, x, 5, 1.0, y=y), mk, nb)
+    record("cfg1_corr_k5", lambda x, y: B.sws_conv1d(x, t1, y=y), mk, nb + 20, 2.0 * 5 * 1048572)
+    del x1
+    # cfg2: [16,64,4096], pool w=3 and conv1d [64,64,3]
+    x2, w2 = workloads.make(2)
+    x2, w2 = g(x2), g(w2)
+    mk = lambda: (x2.clone(), torch.empty(16, 64, 4094, device="cuda"))
+    nb = slide_bytes(1024, 4096, 3)
+    record("cfg2_avgpool_w3", lambda x, y: B.sws_slide1d(0, x, 3, 1 / 3, y=y), mk, nb)
+    record("cfg2_maxpool_w3", lambda x, y: B.sws_slide1d(1, x, 3, 1.0, y=y), mk, nb)
+    record("cfg2_conv1d_64x64x3", lambda x, y: B.sws_conv1d(x, w2, y=y), mk, nb + 4 * 64 * 64 * 3,
+           2.0 * 16 * 64 * 4094 * 64 * 3)
+    del x2
+    # cfg3: [32,64,112,112] 3x3 pad 1, stride 1 and 2
+    x3, _ = workloads.make(3)
+    x3 = g(x3)
+    for s, ho in ((1, 112), (2, 56)):
+        mk = lambda: (x3.clone(), torch.empty(32, 64, ho, ho, device="cuda"))
+        nb = 4 * (2048 * 112 * 112 + 2048 * ho * ho)
+        record("cfg3_maxpool3x3_s%d" % s, lambda x, y: B.sws_pool2d(1, x, 3, 3, s, s, 1, 1, 1.0, y=y), mk, nb)
+        record("cfg3_avgpool3x3_s%d" % s, lambda x, y: B.sws_pool2d(0, x, 3, 3, s, s, 1, 1, 1 / 9, y=y), mk, nb)
+    del x3
+    # cfg4: conv2d [32,64,56,56] x [64,64,3,3], pad 1
+    x4, w4 = workloads.make(4)
+    x4, w4 = g(x4), g(w4)
+    mk = lambda: (x4.clone(), torch.empty(32, 64, 56, 56, device="cuda"))
+    nb = 4 * (2 * 32 * 64 * 56 * 56 + 64 * 64 * 9)
+    record("cfg4_conv2d_3x3", lambda x, y: B.sws_conv2d(x, w4, 1, 1, 1, 1, y=y), mk, nb,
+           2.0 * 32 * 64 * 56 * 56 * 64 * 9)
+    del x4
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline(x_host, taps_host):
+    """The oracle, as it stands, on the first 4096 rows (32 batch items) of configuration 5:
+    the same seven operators.  GB/s on the same algorithmic-byte basis as the GPU figure."""
+    import oracle
+    rows = 4096
+    xs = x_host.reshape(ROWS5, LEN5)[:rows]
+    t0 = time.perf_counter()
+    nbytes = 0
+    for w in WINDOWS5:
+        oracle.slide1d(oracle.OP_ADD, xs, w)
+        oracle.slide1d(oracle.OP_MAX, xs, w)
+        nbytes += 2 * slide_bytes(rows, LEN5, w)
+    oracle.conv1d(xs.reshape(rows // CH5, CH5, LEN5), taps_host, groups=CH5)
+    nbytes += slide_bytes(rows, LEN5, K5) + 4 * CH5 * K5
+    dt = time.perf_counter() - t0
+    return {"value": round(nbytes / dt / 1e9, 4), "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
+            "seconds": round(dt, 3),
+            "sample": "first 4096 of 32768 rows of cfg5, all seven operators (fp64 naive O(w*N), OpenMP over rows)"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (rows / planes / images are independent, so more "
+              "GPUs would each take a slice with no communication); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2305_16513_amd import binding as B, workloads
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.lib()                                       # fail loudly if the HIP library is missing
+
+    x_host, taps_host = workloads.make(5)
+    x = torch.from_numpy(x_host).cuda()
+    taps = torch.from_numpy(taps_host).cuda()
+    outs = {w: torch.empty(256, 128, LEN5 - w + 1, device="cuda") for w in WINDOWS5}
+    y_conv = torch.empty(256, 128, LEN5 - K5 + 1, device="cuda")
+
+    launches = []                                  # (name, fn, algorithmic bytes, flops)
+    for w in WINDOWS5:
+        nb = slide_bytes(ROWS5, LEN5, w)
+        launches.append(("slide_add_w%d" % w, (lambda w=w: B.sws_slide1d(0, x, w, 1.0 / w, y=outs[w])), nb, 0.0))
+        launches.append(("slide_max_w%d" % w, (lambda w=w: B.sws_slide1d(1, x, w, 1.0, y=outs[w])), nb, 0.0))
+    launches.append(("dwconv_k31", lambda: B.sws_conv1d(x, taps, groups=CH5, y=y_conv),
+                     slide_bytes(ROWS5, LEN5, K5) + 4 * CH5 * K5, 2.0 * ROWS5 * (LEN5 - K5 + 1) * K5))
+    step_bytes = sum(l[2] for l in launches)
+
+    def step(events=None):
+        for i, (_, fn, _, _) in enumerate(launches):
+            fn()
+            if events is not None:
+                events[i].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in launches] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        ev0[k].record()
+        step(evs[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    per = [0.0] * len(launches)
+    for k in range(args.steps):
+        prev = ev0[k]
+        for i in range(len(launches)):
+            per[i] += prev.elapsed_time(evs[k][i])
+            prev = evs[k][i]
+    per = [p / args.steps for p in per]            # ms per launch
+    ms_step = wall * 1e3 / args.steps
+
+    kernels = {}
+    for (name, _, nb, fl), ms in zip(launches, per):
+        rec = {"ms": round(ms, 4), "GBps": round(nb / ms / 1e6, 1), "frac_hbm_peak": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+        if fl:
+            rec["GFLOPs"] = round(fl / ms / 1e6, 1)
+        kernels[name] = rec
+
+    # dominant kernel: the one the step spends most time in (the six slide launches share
+    # one kernel template; the depthwise convolution is the other)
+    slide_ms = sum(per[:6])
+    if slide_ms >= per[6]:
+        dom_name = "slide_scan_kernel (sws_slide1d, w in {16,64,255}, add and max)"
+        dom_bytes = sum(l[2] for l in launches[:6]) / 6.0
+        dom_ms = slide_ms / 6.0
+        traffic = read_traffic("slide_scan_cfg5_hbm_traffic.txt")
+    else:
+        dom_name = "depthwise conv kernel (sws_conv1d, k=31, groups=128)"
+        dom_bytes = launches[6][2]
+        dom_ms = per[6]
+        traffic = read_traffic("dwconv_cfg5_hbm_traffic.txt")
+    achieved = dom_bytes / dom_ms / 1e6
+    pool_bytes = sum(l[2] for l in launches[:6])
+    result = {
+        "metric": "sliding pool GB/s (% HBM peak); sliding conv GFLOP/s (% roofline)",
+        "value": round(step_bytes / ms_step / 1e6, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "cfg5_large_window_1d: x[256,128,16384] fp32 U[-1,1]; sliding add+max w in {16,64,255}; "
+                               "depthwise conv k=31; 7 launches per step",
+                   "algorithmic_bytes_per_step": step_bytes},
+        "pool_GBps": round(pool_bytes / slide_ms / 1e6, 1),
+        "pool_frac_hbm_peak": round(pool_bytes / slide_ms / 1e6 / HBM_PEAK_GBPS, 4),
+        "dwconv_GFLOPs": kernels["dwconv_k31"]["GFLOPs"],
+        "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "avg_launch_ms": round(dom_ms, 4), "algorithmic_bytes_per_launch": dom_bytes,
+                     "traffic": traffic},
+        "kernels": kernels,
+    }
+    del outs, y_conv
+    torch.cuda.empty_cache()
+    if not args.no_ops:
+        result["ops"] = ops_table(torch, B, workloads)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(x_host, taps_host)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
