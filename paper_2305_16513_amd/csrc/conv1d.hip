@@ -1,0 +1,176 @@
+// sws_conv1d — 1-D convolution as a sliding sum of shifted, weighted rows (Section 2.5;
+// the Vector Slide loop of Section 3, Algorithm 4, with X <- X + f_t * Slide(...)).
+// The unmodified input row is staged once per tile; no column matrix is ever built.
+//
+//  * conv1d_thin_kernel: one input channel per output channel (depthwise, or a single
+//    sequence).  There is no channel contraction, so this is plain VALU work bounded by
+//    HBM: a lane keeps a window of 16 + k - 1 consecutive inputs in registers and slides
+//    the k taps (held in scalar registers) over it, producing 16 consecutive outputs.
+//    Global traffic is coalesced 128-bit strips; LDS turns strips into per-lane windows
+//    and the per-lane outputs back into strips.
+#include "sws_internal.h"
+
+namespace sws {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWavesPerWg = kThreads / kWave;
+constexpr int kTileOut = 1024;                       // outputs per wave tile (16 per lane)
+
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Position q of a wave tile lives at q + 4*(q/16): 16-byte aligned for strips (q = 4*lane)
+// and for per-lane windows (q = 16*lane + 4*u), and both shapes spread over the banks.
+__host__ __device__ constexpr int lds_pos(int q) { return q + ((q >> 4) << 2); }
+
+template <int KB4>
+__global__ __launch_bounds__(kThreads) void conv1d_thin_kernel(
+    const float *__restrict__ x, const float *__restrict__ wgt, float *__restrict__ y, int L, int Lo, int k,
+    int pad, int Cin, int Cout, int cog, int tiles_per_row, int group, int chunks_per_row, int64_t n_units)
+{
+    constexpr int K4 = 4 * KB4;                      // taps, zero-padded to a multiple of 4
+    constexpr int NI = kTileOut + K4;                // staged inputs per tile
+    constexpr int REGION = lds_pos(NI + 15);
+    __shared__ __attribute__((aligned(16))) float lds[kWavesPerWg * REGION];
+
+    const int64_t unit = xcd_unit(n_units);
+    if (unit < 0) return;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    float *A = lds + wave * REGION;
+    const int64_t ro = unit / chunks_per_row;        // output row = b*Cout + co
+    const int chunk = (int)(unit - ro * chunks_per_row);
+    const int64_t b = ro / Cout;
+    const int co = (int)(ro - b * Cout);
+    const float *xr = x + (b * Cin + co / cog) * (int64_t)L;
+    const float *wr = wgt + (int64_t)co * k;
+    float *yr = y + ro * (int64_t)Lo;
+
+    float f[K4];
+#pragma unroll
+    for (int t = 0; t < K4; ++t) f[t] = (t < k) ? wr[t] : 0.0f;
+
+    int t_end = (chunk + 1) * group;
+    if (t_end > tiles_per_row) t_end = tiles_per_row;
+    for (int t = chunk * group + wave; t < t_end; t += kWavesPerWg) {
+        const int t0 = t * kTileOut;                 // first output of the tile
+        const int p0 = t0 - pad;                     // input position of staged element 0
+        // ---- stage inputs [p0, p0 + NI): four strips plus the k-1 halo
+        if (p0 >= 0 && p0 <= L - NI) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int q = j * 256 + 4 * lane;
+                *(v4f *)(A + lds_pos(q)) = __builtin_nontemporal_load((const v4f_u *)(xr + p0 + q));
+            }
+            if (4 * lane < K4) {
+                const int q = kTileOut + 4 * lane;
+                *(v4f *)(A + lds_pos(q)) = *(const v4f_u *)(xr + p0 + q);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 5; ++j) {
+                const int q = j * 256 + 4 * lane;
+                if (q < NI) {
+                    v4f g;
+                    g.x = (p0 + q + 0 >= 0 && p0 + q + 0 < L) ? xr[p0 + q + 0] : 0.0f;
+                    g.y = (p0 + q + 1 >= 0 && p0 + q + 1 < L) ? xr[p0 + q + 1] : 0.0f;
+                    g.z = (p0 + q + 2 >= 0 && p0 + q + 2 < L) ? xr[p0 + q + 2] : 0.0f;
+                    g.w = (p0 + q + 3 >= 0 && p0 + q + 3 < L) ? xr[p0 + q + 3] : 0.0f;
+                    *(v4f *)(A + lds_pos(q)) = g;
+                }
+            }
+        }
+        wave_lds_sync();
+        // ---- my window: inputs 16*lane .. 16*lane + K4 + 15
+        float xw[K4 + 16];
+#pragma unroll
+        for (int u = 0; u < KB4 + 4; ++u) {
+            const v4f g = *(const v4f *)(A + lds_pos(16 * lane) + lds_pos(4 * u));
+            xw[4 * u] = g.x; xw[4 * u + 1] = g.y; xw[4 * u + 2] = g.z; xw[4 * u + 3] = g.w;
+        }
+        // ---- slide the taps: acc[e] = sum_t f[t] * x[e + t]
+        float acc[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
+#pragma unroll
+        for (int tt = 0; tt < K4; ++tt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[e] = fmaf(f[tt], xw[e + tt], acc[e]);
+        wave_lds_sync();                             // every lane has its window: A may be reused
+        // ---- per-lane outputs -> strips
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            *(v4f *)(A + lds_pos(16 * lane) + 4 * u) =
+                (v4f){acc[4 * u], acc[4 * u + 1], acc[4 * u + 2], acc[4 * u + 3]};
+        wave_lds_sync();
+        const int lim = Lo - t0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int q = j * 256 + 4 * lane;
+            if (q >= lim) continue;
+            const v4f o = *(const v4f *)(A + lds_pos(q));
+            if (q + 4 <= lim) {
+                __builtin_nontemporal_store(o, (v4f_u *)(yr + t0 + q));
+            } else {
+                yr[t0 + q] = o.x;
+                if (q + 1 < lim) yr[t0 + q + 1] = o.y;
+                if (q + 2 < lim) yr[t0 + q + 2] = o.z;
+            }
+        }
+        wave_lds_sync();
+    }
+}
+
+template <int KB4>
+hipError_t launch_thin(const float *x, const float *wgt, float *y, int64_t rows_out, int L, int Lo, int k, int pad,
+                       int Cin, int Cout, int cog, hipStream_t s)
+{
+    const int tiles_per_row = (Lo + kTileOut - 1) / kTileOut;
+    int64_t g = rows_out * tiles_per_row / 2048;
+    if (g < kWavesPerWg) g = kWavesPerWg;
+    if (g > tiles_per_row) g = tiles_per_row;
+    const int group = (int)g;
+    const int chunks_per_row = (tiles_per_row + group - 1) / group;
+    const int64_t n_units = rows_out * chunks_per_row;
+    const int64_t grid = xcd_grid(n_units);
+    if (grid > 2147483647LL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((conv1d_thin_kernel<KB4>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, wgt, y, L, Lo, k,
+                       pad, Cin, Cout, cog, tiles_per_row, group, chunks_per_row, n_units);
+    return hipGetLastError();
+}
+
+constexpr int kThinMaxK = 64;
+
+}  // namespace
+
+hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin, int64_t L,
+                         int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad, int32_t dilation,
+                         int32_t groups, hipStream_t s)
+{
+    int variant = g_opt.conv1d_variant;
+    const bool thin_ok = (Cin / groups == 1) && stride == 1 && dilation == 1 && k <= kThinMaxK;
+    if (variant == 2 && !thin_ok) variant = 0;
+    if (variant == 0) variant = thin_ok ? 2 : 1;
+    if (variant == 2) {
+        const int cog = (int)(Cout / groups);
+#define SWS_THIN(KB)                                                                                            \
+    case KB:                                                                                                    \
+        return launch_thin<KB>(x, wgt, y, B * Cout, (int)L, (int)Lo, k, pad, (int)Cin, (int)Cout, cog, s)
+        switch ((k + 3) / 4) {
+            SWS_THIN(1); SWS_THIN(2); SWS_THIN(3); SWS_THIN(4); SWS_THIN(5); SWS_THIN(6); SWS_THIN(7); SWS_THIN(8);
+            SWS_THIN(9); SWS_THIN(10); SWS_THIN(11); SWS_THIN(12); SWS_THIN(13); SWS_THIN(14); SWS_THIN(15);
+            SWS_THIN(16);
+        default: break;
+        }
+#undef SWS_THIN
+    }
+    return launch_conv1d_naive(x, wgt, y, B, Cin, L, Cout, Lo, k, stride, pad, dilation, groups, s);
+}
+
+}  // namespace sws

@@ -10,13 +10,6 @@ hipError_t launch_pool2d(int op, const float *x, float *y, int64_t planes, int64
     return launch_pool2d_naive(op, x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, s);
 }
 
-hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin, int64_t L,
-                         int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad, int32_t dilation,
-                         int32_t groups, hipStream_t s)
-{
-    return launch_conv1d_naive(x, wgt, y, B, Cin, L, Cout, Lo, k, stride, pad, dilation, groups, s);
-}
-
 hipError_t launch_conv2d(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
                          int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh,
                          int32_t sw, int32_t ph, int32_t pw, hipStream_t s)
