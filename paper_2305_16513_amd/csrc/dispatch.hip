@@ -1,14 +1,7 @@
-// Kernel selection for pooling and convolution.
+// Kernel selection for 2-D convolution.
 #include "sws_internal.h"
 
 namespace sws {
-
-hipError_t launch_pool2d(int op, const float *x, float *y, int64_t planes, int64_t H, int64_t W, int64_t Ho,
-                         int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
-                         float scale, hipStream_t s)
-{
-    return launch_pool2d_naive(op, x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, s);
-}
 
 hipError_t launch_conv2d(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
                          int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh,
