@@ -2,6 +2,8 @@
 // the Vector Slide loop of Section 3, Algorithm 4, with X <- X + f_t * Slide(...)).
 // The unmodified input row is staged once per tile; no column matrix is ever built.
 //
+//  * dense channels (groups = 1): handed to the matrix-core kernel of conv_mfma.hip.
+//
 //  * conv1d_thin_kernel: one input channel per output channel (depthwise, or a single
 //    sequence).  There is no channel contraction, so this is plain VALU work bounded by
 //    HBM: a lane keeps a window of 16 + k - 1 consecutive inputs in registers and slides
@@ -155,8 +157,17 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
 {
     int variant = g_opt.conv1d_variant;
     const bool thin_ok = (Cin / groups == 1) && stride == 1 && dilation == 1 && k <= kThinMaxK;
+    const bool dense_ok = groups == 1 && Cin >= 2 && stride == 1 && dilation == 1;
     if (variant == 2 && !thin_ok) variant = 0;
-    if (variant == 0) variant = thin_ok ? 2 : 1;
+    if (variant == 3 && !dense_ok) variant = 0;
+    if (variant == 0) variant = thin_ok ? 2 : (dense_ok ? 3 : 1);
+    if (variant == 3) {
+        // the dense contraction is the 2-D kernel on images of height 1
+        bool taken = false;
+        const hipError_t e = launch_conv2d_mfma(x, wgt, y, B, Cin, 1, L, Cout, 1, Lo, 1, k, 0, pad, s, &taken);
+        if (taken) return e;
+        variant = 1;
+    }
     if (variant == 2) {
         const int cog = (int)(Cout / groups);
 #define SWS_THIN(KB)                                                                                            \
