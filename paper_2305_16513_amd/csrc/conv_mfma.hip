@@ -8,123 +8,218 @@
 // zero padding) is staged ONCE in LDS per block of input channels and is read at kh*kw
 // shifted offsets; the column matrix of im2col never exists.
 //
-// Tile geometry.  A workgroup (4 wavefronts) computes 64 output channels for NP = 128*NBW
-// output positions of one image.  Positions are numbered p = r*Wt + c over a tile of TR
-// rows with pitch Wt = TC + kw - 1 (the staged row length), so that the input of tap
-// (a, b) for position p is simply LDS element p + a*Wt + b: a shifted read of the same
-// buffer.  Columns c >= TC are computed and thrown away.
+// Tile geometry.  A workgroup computes 64 output channels for NP output positions of one
+// image; each wavefront owns MB 32-channel blocks x NBW 32-position blocks of accumulators.
+// Two ways to cut an image into tiles:
+//   mode A (narrow images): NP consecutive positions of the flattened Ho*Wo output, which
+//          span a few whole rows; the staged rows are full width plus halo.
+//   mode B (wide images, and 1-D convolution as height 1): NP consecutive positions of one
+//          output row; the staged rows are that column range plus halo.
+// Either way a lane knows the LDS offset of its position inside the staged tile (row pitch
+// Wt), and the input of tap (a, b) is that offset + a*Wt + b: a shifted read.
 //
 // MFMA operand layout (32x32x2, wave64): lane l supplies A[i = l%32][k = l/32] and
 // B[k = l/32][j = l%32]; accumulator register v of lane l holds
 // D[i = 8*(v/4) + 4*(l/32) + v%4][j = l%32].
+//
+// Pipeline per block of CIB input channels: the global loads of block i+1 are issued into
+// registers before the MFMA loop of block i and written to LDS after it, so their latency
+// hides behind the matrix work.
 #include "sws_internal.h"
 
 namespace sws {
 
 namespace {
 
-constexpr int kThreads = 256;
 constexpr int kCoTile = 64;                           // output channels per workgroup
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 struct ConvGeom {
     int Cin, H, W, Cout, Ho, Wo, kh, kw, ph, pw;
-    int TR, TC, Wt, NRows, CP;                        // tile rows / cols, staged pitch, staged rows, channel pitch
-    int tiles_r, tiles_c, co_blocks;
+    int mode_b;                                       // 0: flat tiles over rows, 1: column tiles of one row
+    int NP;                                           // output positions per workgroup
+    int Wt, NRows, CP;                                // staged row pitch, staged rows, channel pitch in LDS
+    int CH;                                           // 64-column chunks per staged row
+    int tiles_per_img, tiles_c, co_blocks;
 };
 
-template <int NBW, int CIB>
-__global__ __launch_bounds__(kThreads) void conv2d_mfma_kernel(const float *__restrict__ x,
-                                                               const float *__restrict__ wgt,
-                                                               float *__restrict__ y, ConvGeom g,
-                                                               int64_t n_units)
+// x / d for 0 <= x < 2^20 and 1 <= d < 2^12, exact, a handful of VALU ops instead of the
+// long integer-division sequence (the margin 0.5/d dwarfs the fp32 rounding of the product).
+__device__ __forceinline__ int fast_div(int x, float inv_d) { return (int)(((float)x + 0.5f) * inv_d); }
+
+template <int WAVES, int MB, int NBW, int CIB>
+__global__ __launch_bounds__(WAVES * 64) void conv2d_mfma_kernel(const float *__restrict__ x,
+                                                                 const float *__restrict__ wgt,
+                                                                 float *__restrict__ y, ConvGeom g,
+                                                                 int64_t n_units)
 {
+    constexpr int THREADS = WAVES * 64;
+    constexpr int MG = 2 / MB;                        // wave groups along the 64 output channels
     constexpr int KP = CIB / 2;                       // k-pairs (MFMA steps) per tap and channel block
+    constexpr int XS = (CIB == 16 ? 128 : 64) / WAVES;    // staged-input registers per lane
+    constexpr int WS = (2304 + THREADS - 1) / THREADS;    // staged-weight 128-bit registers per lane
     extern __shared__ __attribute__((aligned(16))) float lds[];
     float *Xl = lds;                                  // [CIB][CP] staged inputs
-    float *Wl = lds + CIB * g.CP;                     // [tap][KP][2][64] weights, co fastest
+    float *Wl = lds + CIB * g.CP;                     // [64 co][WP] weights of the block, as in memory
 
     const int64_t unit = xcd_unit(n_units);
     if (unit < 0) return;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l32 = lane & 31, half = lane >> 5;
+    const int wm = wave % MG, wn = wave / MG;         // my channel group, my position group
 
-    // unit -> (image, co block, tile row, tile col)
+    // unit -> (image, co block, tile)
     int64_t u = unit;
-    const int tc = (int)(u % g.tiles_c); u /= g.tiles_c;
-    const int tr = (int)(u % g.tiles_r); u /= g.tiles_r;
+    const int tile = (int)(u % g.tiles_per_img); u /= g.tiles_per_img;
     const int cb = (int)(u % g.co_blocks); u /= g.co_blocks;
     const int64_t n = u;
-    const int oh0 = tr * g.TR, ow0 = tc * g.TC;
     const int co0 = cb * kCoTile;
     const int KT = g.kh * g.kw;
-    const int64_t plane = (int64_t)g.H * g.W;
-    const float *xn = x + n * g.Cin * plane;
+    const int plane = g.H * g.W;
+    const float *xn = x + n * g.Cin * (int64_t)plane;
 
-    v16f acc[2][NBW];
+    // tile origin: first output row / column, and the input coordinates of staged (0, 0)
+    int oh_first, ow_first, p_base = 0;
+    if (g.mode_b) {
+        oh_first = tile / g.tiles_c;
+        ow_first = (tile - oh_first * g.tiles_c) * g.NP;
+    } else {
+        p_base = tile * g.NP;
+        oh_first = p_base / g.Wo;
+        ow_first = 0;
+    }
+    const int row0 = oh_first - g.ph, col0 = ow_first - g.pw;
+
+    // my positions: validity, output coordinates, offset inside the staged tile
+    int oh[NBW], ow[NBW], boff[NBW];
+    bool pok[NBW];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int nb = 0; nb < NBW; ++nb) {
+        const int idx = (wn * NBW + nb) * 32 + l32;
+        if (g.mode_b) {
+            oh[nb] = oh_first;
+            ow[nb] = ow_first + idx;
+            pok[nb] = ow[nb] < g.Wo;
+        } else {
+            const int p = p_base + idx;
+            oh[nb] = p / g.Wo;
+            ow[nb] = p - oh[nb] * g.Wo;
+            pok[nb] = p < g.Ho * g.Wo;
+        }
+        boff[nb] = half * g.CP + (pok[nb] ? (oh[nb] - oh_first) * g.Wt + (ow[nb] - ow_first) : 0);
+    }
+
+    v16f acc[MB][NBW];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.0f;
 
-    const int a_lane0 = half * 64 + ((l32 + 32 * half) & 63);          // + mb*32 stays inside 0..63
-    const int a_lane1 = half * 64 + ((32 + l32 + 32 * half) & 63);
-    const int b_lane = half * g.CP + (wave * NBW) * 32 + l32;
+    // Weights sit in LDS as 64 rows (output channels) of per_co = CIB*KT floats in memory order
+    // (channel-major, tap fastest) with pitch WP = per_co + 2.  WP == 2 (mod 4) spreads 32
+    // consecutive channels over 32 distinct even banks, and the k = 1 half of the wave reads KT
+    // floats further on: the odd banks when KT is odd.
+    const int per_co = CIB * KT;
+    const int WP = per_co + 2;
+    const int a_lane = (wm * MB * 32 + l32) * WP + half * KT;
 
+    // Staging plan, fixed for the whole kernel.  Input segments (channel, staged row, 64-column
+    // chunk) are dealt to the wavefronts round-robin; slot s of this lane moves one float of
+    // segment wave + WAVES*s.  xg = offset of that float inside the channel block (-1: always
+    // zero), xl = its LDS offset (-1: nothing to write).  Everything is straight-line code so
+    // that all loads of a block are in flight together.
+    const int nseg = CIB * g.NRows * g.CH;
+    const float inv_rc = 1.0f / (float)(g.NRows * g.CH), inv_c = 1.0f / (float)g.CH;
+    int xg[XS], xl[XS];
+#pragma unroll
+    for (int s = 0; s < XS; ++s) {
+        const int seg = wave + WAVES * s;
+        const int ci = fast_div(seg, inv_rc);
+        const int r2 = seg - ci * g.NRows * g.CH;
+        const int rr = fast_div(r2, inv_c), ch = r2 - rr * g.CH;
+        const int gh = row0 + rr, cc = ch * 64 + lane, gw = col0 + cc;
+        const bool act = seg < nseg && cc < g.Wt;
+        xl[s] = act ? ci * g.CP + rr * g.Wt + cc : -1;
+        xg[s] = (act && gh >= 0 && gh < g.H && gw >= 0 && gw < g.W) ? ci * plane + gh * g.W + gw : -1;
+    }
+    // Weight block: 64 runs (one per output channel) of per_co contiguous floats, moved as
+    // 128-bit pieces; piece f = tid + THREADS*s belongs to channel f / (per_co/4).
+    const int pf4 = per_co / 4, nf4 = kCoTile * pf4;
+    const float inv_pf4 = 1.0f / (float)pf4;
+    int wg[WS], wl[WS];
+#pragma unroll
+    for (int s = 0; s < WS; ++s) {
+        const int f = threadIdx.x + THREADS * s;
+        const int co = fast_div(f, inv_pf4), j4 = f - co * pf4;
+        const bool ok = f < nf4 && co0 + co < g.Cout;
+        wg[s] = ok ? (co0 + co) * g.Cin * KT + 4 * j4 : -1;
+        wl[s] = f < nf4 ? co * WP + 4 * j4 : -1;
+    }
+
+    float xreg[XS];
+    v4f wreg[WS];
+
+    // Loads are unconditional (out-of-range slots read element 0 of the image / of the weights,
+    // which is valid memory) and the validity test is applied when the registers are written to
+    // LDS, on the far side of the matrix loop: nothing forces a wait on a single load.
+    auto prefetch = [&](int ci0) {
+        const int xb = ci0 * plane;
+#pragma unroll
+        for (int s = 0; s < XS; ++s) xreg[s] = xn[xg[s] >= 0 ? xb + xg[s] : 0];
+        const int wb = ci0 * KT;
+#pragma unroll
+        for (int s = 0; s < WS; ++s) wreg[s] = *(const v4f_u *)(wgt + (wg[s] >= 0 ? wb + wg[s] : 0));
+    };
+
+    auto commit = [&]() {
+#pragma unroll
+        for (int s = 0; s < XS; ++s)
+            if (xl[s] >= 0) Xl[xl[s]] = xg[s] >= 0 ? xreg[s] : 0.0f;
+#pragma unroll
+        for (int s = 0; s < WS; ++s) {
+            if (wl[s] >= 0) {
+                const v4f v = wg[s] >= 0 ? wreg[s] : (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+                *(v2f *)(Wl + wl[s]) = (v2f){v.x, v.y};          // rows are 8-byte aligned (WP is even)
+                *(v2f *)(Wl + wl[s] + 2) = (v2f){v.z, v.w};
+            }
+        }
+    };
+
+    // zero the part of every channel slab that staging never writes (read by discarded lanes only)
+    {
+        const int used = g.NRows * g.Wt, tail = g.CP - used;
+        for (int i = threadIdx.x; i < CIB * tail; i += THREADS) {
+            const int ci = i / tail, o = i - ci * tail;
+            Xl[ci * g.CP + used + o] = 0.0f;
+        }
+    }
+
+    prefetch(0);
     for (int ci0 = 0; ci0 < g.Cin; ci0 += CIB) {
-        __syncthreads();                              // previous block fully consumed
-        // ---- stage inputs: rows of the tile, zero outside the image, zero tail up to CP
-        for (int rowid = wave; rowid < CIB * g.NRows; rowid += 4) {
-            const int ci = rowid / g.NRows, rr = rowid - ci * g.NRows;
-            const int gh = oh0 + rr - g.ph;
-            const bool row_ok = (ci0 + ci < g.Cin) && gh >= 0 && gh < g.H;
-            const float *src = xn + (int64_t)(ci0 + ci) * plane + (int64_t)gh * g.W;
-            for (int cc = lane; cc < g.Wt; cc += 64) {
-                const int gw = ow0 + cc - g.pw;
-                Xl[ci * g.CP + rr * g.Wt + cc] = (row_ok && gw >= 0 && gw < g.W) ? src[gw] : 0.0f;
-            }
-        }
-        {
-            const int used = g.NRows * g.Wt, tail = g.CP - used;
-            for (int i = threadIdx.x; i < CIB * tail; i += kThreads) {
-                const int ci = i / tail, o = i - ci * tail;
-                Xl[ci * g.CP + used + o] = 0.0f;
-            }
-        }
-        // ---- stage weights: lane = output channel, (ci, tap) walks the contiguous block
-        {
-            const int per_co = CIB * KT;
-            const bool co_ok = co0 + lane < g.Cout;
-            const float *wsrc = wgt + ((int64_t)(co0 + lane) * g.Cin + ci0) * KT;
-            for (int j = wave; j < per_co; j += 4) {
-                const int ci = j / KT, tap = j - ci * KT;
-                const float v = (co_ok && ci0 + ci < g.Cin) ? wsrc[j] : 0.0f;
-                Wl[((tap * KP + (ci >> 1)) * 2 + (ci & 1)) * 64 + ((lane + 32 * (ci & 1)) & 63)] = v;
-            }
-        }
+        __syncthreads();                              // the previous block has been consumed
+        commit();
         __syncthreads();
-        // ---- taps x channel pairs on the matrix cores
+        if (ci0 + CIB < g.Cin) prefetch(ci0 + CIB);   // in flight during the matrix work below
         int ta = 0, tb = 0;
         for (int tap = 0; tap < KT; ++tap) {
             const int shift = ta * g.Wt + tb;
-            const float *wt = Wl + tap * KP * 128;
-            const float *xt = Xl + b_lane + shift;
+            const float *wt = Wl + tap + a_lane;
 #pragma unroll
             for (int kp = 0; kp < KP; ++kp) {
-                const float a0 = wt[kp * 128 + a_lane0];
-                const float a1 = wt[kp * 128 + a_lane1];
-                float b[NBW];
+                float a[MB], b[NBW];
 #pragma unroll
-                for (int nb = 0; nb < NBW; ++nb) b[nb] = xt[2 * kp * g.CP + nb * 32];
+                for (int mb = 0; mb < MB; ++mb) a[mb] = wt[2 * kp * KT + mb * 32 * WP];
 #pragma unroll
-                for (int nb = 0; nb < NBW; ++nb) {
-                    acc[0][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b[nb], acc[0][nb], 0, 0, 0);
-                    acc[1][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b[nb], acc[1][nb], 0, 0, 0);
-                }
+                for (int nb = 0; nb < NBW; ++nb) b[nb] = Xl[2 * kp * g.CP + boff[nb] + shift];
+#pragma unroll
+                for (int nb = 0; nb < NBW; ++nb)
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mb], b[nb], acc[mb][nb], 0, 0, 0);
             }
             if (++tb == g.kw) { tb = 0; ++ta; }
         }
@@ -134,56 +229,54 @@ __global__ __launch_bounds__(kThreads) void conv2d_mfma_kernel(const float *__re
     float *yn = y + n * g.Cout * (int64_t)g.Ho * g.Wo;
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb) {
-        const int p = (wave * NBW + nb) * 32 + l32;
-        const int r = p / g.Wt, c = p - r * g.Wt;
-        const int oh = oh0 + r, ow = ow0 + c;
-        if (r >= g.TR || c >= g.TC || oh >= g.Ho || ow >= g.Wo) continue;
+        if (!pok[nb]) continue;
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+        for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int co = co0 + mb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                if (co < g.Cout) yn[((int64_t)co * g.Ho + oh) * g.Wo + ow] = acc[mb][nb][v];
+                const int co = co0 + (wm * MB + mb) * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                if (co < g.Cout) yn[((int64_t)co * g.Ho + oh[nb]) * g.Wo + ow[nb]] = acc[mb][nb][v];
             }
     }
 }
 
-template <int NBW>
-bool plan(ConvGeom &g, int64_t N, int64_t *n_units, size_t *lds_bytes, int CIB)
+bool plan(ConvGeom &g, int NP, int CIB, int xslots_total, int64_t N, int64_t *n_units, size_t *lds_bytes)
 {
-    const int NP = 128 * NBW;
-    if (g.Wo + g.kw - 1 <= NP) {                      // full-width tiles, several rows
-        g.TC = g.Wo;
-        g.Wt = g.TC + g.kw - 1;
-        g.TR = NP / g.Wt;
-        if (g.TR > g.Ho) g.TR = g.Ho;
-    } else {                                          // one row, column tiles
-        g.TR = 1;
-        g.Wt = NP;
-        g.TC = NP - g.kw + 1;
-        if (g.TC < 1) return false;
+    g.NP = NP;
+    if (g.Wo + g.kw - 1 <= 192) {                     // mode A: flat tiles, full-width rows
+        g.mode_b = 0;
+        g.Wt = g.Wo + g.kw - 1;
+        const int rows = (g.NP + g.Wo - 2) / g.Wo + 1;                 // output rows a tile can touch
+        g.NRows = (rows < g.Ho ? rows : g.Ho) + g.kh - 1;
+        g.tiles_c = 1;
+        g.tiles_per_img = (g.Ho * g.Wo + g.NP - 1) / g.NP;
+    } else {                                          // mode B: column tiles of single rows
+        g.mode_b = 1;
+        g.Wt = g.NP + g.kw - 1;
+        g.NRows = g.kh;
+        g.tiles_c = (g.Wo + g.NP - 1) / g.NP;
+        g.tiles_per_img = g.Ho * g.tiles_c;
     }
-    g.NRows = g.TR + g.kh - 1;
-    int need = NP + (g.kh - 1) * g.Wt + g.kw;         // furthest shifted read, any lane
-    if (need < g.NRows * g.Wt) need = g.NRows * g.Wt;
+    g.CH = (g.Wt + 63) / 64;
+    const int need = g.NRows * g.Wt;
     g.CP = (need + 31) / 64 * 64 + 32;                // == 32 (mod 64): the two k-halves of a wave
-    if (g.CP < need) g.CP += 64;                      //   hit disjoint LDS banks
-    g.tiles_r = (g.Ho + g.TR - 1) / g.TR;
-    g.tiles_c = (g.Wo + g.TC - 1) / g.TC;
+                                                      //   read disjoint LDS banks
     g.co_blocks = (g.Cout + kCoTile - 1) / kCoTile;
-    *n_units = N * g.co_blocks * g.tiles_r * g.tiles_c;
-    *lds_bytes = 4 * ((size_t)CIB * g.CP + (size_t)g.kh * g.kw * (CIB / 2) * 128);
-    return *lds_bytes <= 64 * 1024;
+    *n_units = N * g.co_blocks * g.tiles_per_img;
+    *lds_bytes = 4 * ((size_t)CIB * g.CP + (size_t)kCoTile * (CIB * g.kh * g.kw + 2));
+    const int nseg = CIB * g.NRows * g.CH;
+    return *lds_bytes <= 64 * 1024 && nseg <= xslots_total && kCoTile * (CIB * g.kh * g.kw / 4) <= 2304 &&
+           (int64_t)g.Cin * g.H * g.W < 2147483647LL;
 }
 
-template <int NBW, int CIB>
+template <int WAVES, int MB, int NBW, int CIB>
 hipError_t launch(const float *x, const float *wgt, float *y, const ConvGeom &g, int64_t n_units, size_t lds_bytes,
                   hipStream_t s)
 {
     const int64_t grid = xcd_grid(n_units);
     if (grid > 2147483647LL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((conv2d_mfma_kernel<NBW, CIB>), dim3((unsigned)grid), dim3(kThreads), lds_bytes, s, x, wgt, y,
-                       g, n_units);
+    hipLaunchKernelGGL((conv2d_mfma_kernel<WAVES, MB, NBW, CIB>), dim3((unsigned)grid), dim3(WAVES * 64), lds_bytes,
+                       s, x, wgt, y, g, n_units);
     return hipGetLastError();
 }
 
@@ -197,25 +290,23 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
 {
     *taken = false;
     const int KT = kh * kw;
-    const int CIB = (KT <= 9) ? 16 : (KT <= 36 ? 4 : 0);
-    if (CIB == 0 || Cin < 2) return hipSuccess;
+    // channel blocks of 16 (or 4 for big kernels / odd channel counts) must divide Cin
+    const int CIB = (KT <= 9 && Cin % 16 == 0) ? 16 : ((KT <= 36 && Cin % 4 == 0) ? 4 : 0);
+    if (CIB == 0 || Ho * Wo > 2147483647LL / 2 || Cout * Cin * KT > 2147483647LL / 2) return hipSuccess;
     ConvGeom g;
     g.Cin = (int)Cin; g.H = (int)H; g.W = (int)W; g.Cout = (int)Cout; g.Ho = (int)Ho; g.Wo = (int)Wo;
     g.kh = kh; g.kw = kw; g.ph = ph; g.pw = pw;
-    ConvGeom g2 = g, g1 = g;
-    int64_t u2 = 0, u1 = 0;
-    size_t l2 = 0, l1 = 0;
-    const bool ok2 = plan<2>(g2, N, &u2, &l2, CIB);
-    const bool ok1 = plan<1>(g1, N, &u1, &l1, CIB);
-    const bool use2 = ok2 && (u2 >= 512 || !ok1);
-    if (!use2 && !ok1) return hipSuccess;
+    int64_t units = 0;
+    size_t lds = 0;
+    if (!plan(g, 128, CIB, CIB == 16 ? 128 : 64, N, &units, &lds)) return hipSuccess;
     *taken = true;
-    if (use2) {
-        if (CIB == 16) return launch<2, 16>(x, wgt, y, g2, u2, l2, s);
-        return launch<2, 4>(x, wgt, y, g2, u2, l2, s);
+    if (g_opt.conv2d_variant == 3) {                  // 4 wavefronts, two channel blocks each
+        if (CIB == 16) return launch<4, 2, 1, 16>(x, wgt, y, g, units, lds, s);
+        return launch<4, 2, 1, 4>(x, wgt, y, g, units, lds, s);
     }
-    if (CIB == 16) return launch<1, 16>(x, wgt, y, g1, u1, l1, s);
-    return launch<1, 4>(x, wgt, y, g1, u1, l1, s);
+    // 8 wavefronts, one 32x32 accumulator block each: short workgroups, four waves per SIMD
+    if (CIB == 16) return launch<8, 1, 1, 16>(x, wgt, y, g, units, lds, s);
+    return launch<8, 1, 1, 4>(x, wgt, y, g, units, lds, s);
 }
 
 }  // namespace sws
