@@ -49,7 +49,7 @@ struct ConvGeom {
 __device__ __forceinline__ int fast_div(int x, float inv_d) { return (int)(((float)x + 0.5f) * inv_d); }
 
 template <int WAVES, int MB, int NBW, int CIB>
-__global__ __launch_bounds__(WAVES * 64) void conv2d_mfma_kernel(const float *__restrict__ x,
+__global__ __launch_bounds__(WAVES * 64, 2) void conv2d_mfma_kernel(const float *__restrict__ x,
                                                                  const float *__restrict__ wgt,
                                                                  float *__restrict__ y, ConvGeom g,
                                                                  int64_t n_units)
