@@ -38,6 +38,10 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ops", action="store_true", help="skip the per-operator table of configs 1-4")
+    ap.add_argument("--only", default=None,
+                    help="profiling aid: launch just this operator --steps times and print nothing but a "
+                         "short note (names: the keys of 'kernels' and 'ops', or 'copy' for the 2 GiB "
+                         "calibration copy)")
     return ap.parse_args()
 
 
@@ -143,6 +147,50 @@ def ops_table(torch, B, workloads, iters=20):
     return out
 
 
+def run_only(torch, B, workloads, name, steps):
+    """Launch one operator `steps` times (for rocprofv3 runs that should see a single kernel)."""
+    g = lambda a: torch.from_numpy(a).cuda()
+    if name == "copy":
+        src = torch.rand(ROWS5, LEN5, device="cuda")
+        dst = torch.empty_like(src)
+        fn = lambda: B.sws_copy(src, dst)
+    elif name.startswith("slide_") or name == "dwconv_k31":
+        x_host, taps_host = workloads.make(5)
+        x = g(x_host)
+        if name == "dwconv_k31":
+            taps = g(taps_host)
+            y = torch.empty(256, 128, LEN5 - K5 + 1, device="cuda")
+            fn = lambda: B.sws_conv1d(x, taps, groups=CH5, y=y)
+        else:
+            _, opn, wn = name.split("_")
+            w = int(wn[1:])
+            y = torch.empty(256, 128, LEN5 - w + 1, device="cuda")
+            fn = lambda: B.sws_slide1d(0 if opn == "add" else 1, x, w, 1.0 / w, y=y)
+    elif name.startswith("cfg3_"):
+        x3 = g(workloads.make(3)[0])
+        s = int(name[-1])
+        ho = 112 if s == 1 else 56
+        y = torch.empty(32, 64, ho, ho, device="cuda")
+        op = 1 if "max" in name else 0
+        fn = lambda: B.sws_pool2d(op, x3, 3, 3, s, s, 1, 1, 1 / 9, y=y)
+    elif name == "cfg4_conv2d_3x3":
+        x4, w4 = workloads.make(4)
+        x4, w4 = g(x4), g(w4)
+        y = torch.empty(32, 64, 56, 56, device="cuda")
+        fn = lambda: B.sws_conv2d(x4, w4, 1, 1, 1, 1, y=y)
+    elif name == "cfg2_conv1d_64x64x3":
+        x2, w2 = workloads.make(2)
+        x2, w2 = g(x2), g(w2)
+        y = torch.empty(16, 64, 4094, device="cuda")
+        fn = lambda: B.sws_conv1d(x2, w2, y=y)
+    else:
+        raise SystemExit("bench.py --only: unknown operator %r" % name)
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    print(json.dumps({"only": name, "launches": steps}))
+
+
 def cpu_baseline(x_host, taps_host):
     """The oracle, as it stands, on the first 4096 rows (32 batch items) of configuration 5:
     the same seven operators.  GB/s on the same algorithmic-byte basis as the GPU figure."""
@@ -175,6 +223,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     B.lib()                                       # fail loudly if the HIP library is missing
+    if args.only:
+        run_only(torch, B, workloads, args.only, args.steps)
+        return
 
     x_host, taps_host = workloads.make(5)
     x = torch.from_numpy(x_host).cuda()
