@@ -112,9 +112,9 @@ int64_t sws_out_len(int64_t len, int32_t w, int32_t stride, int32_t pad, int32_t
 const char *sws_status_string(int status);
 
 /* Developer knobs for A/B measurements (not needed for normal use; not thread-safe).
- * Known keys: "slide_variant", "pool2d_variant", "conv1d_variant", "conv2d_variant"
- * (0 = automatic choice) and "slide_chunk".  Returns SWS_ERR_INVALID_ARG for an
- * unknown key. */
+ * Known keys: "slide_variant", "pool2d_variant", "conv1d_variant", "conv2d_variant",
+ * "copy_variant" (0 = automatic choice), "slide_chunk" (tiling / store-policy bits) and
+ * "slide_group" (tiles per workgroup).  Returns SWS_ERR_INVALID_ARG for an unknown key. */
 sws_status sws_set_option(const char *key, int64_t value);
 
 /* Library version, "major.minor". */

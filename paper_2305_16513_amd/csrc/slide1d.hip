@@ -2,12 +2,13 @@
 //
 // Two tuned kernels plus the direct-evaluation fallback:
 //
-//  * slide_direct_kernel (small windows): the Vector Slide idea of Section 3 (Algorithm 4)
-//    — the output vector is the (+) of w shifted copies of the input vector.  A lane owns
-//    four consecutive outputs and reads its shifted operands as 128-bit loads at +4, +8
-//    elements, which hit the same cache lines its neighbours fetch.
+//  * slide_direct_kernel: the Vector Slide idea of Section 3 (Algorithm 4) — the output
+//    vector is the (+) of w shifted copies of the input vector.  A lane owns four consecutive
+//    outputs and reads its shifted operands as 128-bit loads at +4, +8 elements.  The
+//    re-read lines cost more than the scan below even at w = 2 (measured), so it is the
+//    default only for w = 1 (a scaled copy) and otherwise an A/B variant for w <= 9.
 //
-//  * slide_scan_kernel (large windows): the block form of the Vector Input algorithm
+//  * slide_scan_kernel (every w >= 2): the block form of the Vector Input algorithm
 //    (Section 3, Algorithm 2).  A wavefront owns a tile of 64*C consecutive inputs cut
 //    into segments of length S = w-1 (counted from the tile origin).  It builds
 //       Pre[q] = x[seg_start(q)] (+) ... (+) x[q]      (in-segment prefix sums, "X1")
@@ -124,46 +125,87 @@ __global__ __launch_bounds__(kThreads) void slide_direct_kernel(const float *__r
 // ------------------------------------------------------------------------------------------
 // Large windows: in-segment prefix + suffix sums, one (+) per output.
 // ------------------------------------------------------------------------------------------
-// LDS layout of one wave tile: local position q lives at q + 4*(q/16).  The 4-float pad
-// after every 16 floats makes both access shapes cheap: strips (lane l <-> q = 4*l) and
-// chunks (lane l <-> q = C*l .. C*l+C-1) are 16-byte aligned and spread over the banks.
-__device__ __forceinline__ int lds_pos(int q) { return q + ((q >> 4) << 2); }
+// LDS layout of one wave tile.  The tile is 16 rows of 64 floats (= 16 groups of 4); group c
+// of row r is stored at group (c ^ (r & 3)) of the same row.  Both access shapes then cover
+// all 64 banks exactly once per 16 lanes of a 128-bit access: strips (16 consecutive lanes
+// read one whole row) and chunks (lane l reads the 4 groups 4*l .. 4*l+3, 16 lanes span 4
+// rows whose group sets the XOR makes disjoint).
+__device__ __forceinline__ int lds_pos(int q)
+{
+    return (q & ~63) | (((((q >> 2) & 15) ^ ((q >> 6) & 3))) << 2) | (q & 3);
+}
+
+// In-segment scan step with the reset folded into arithmetic: acc is forgotten where a new
+// segment starts.  The per-element mask is a lane constant (see seg_mask) — one VALU op for
+// ADD (fma with 0/1), two for MAX / MIN (clamp against -/+inf, then combine).
+template <int OP> struct SegStep;
+template <> struct SegStep<SWS_OP_ADD> {
+    static __device__ __forceinline__ float mask(bool start) { return start ? 0.0f : 1.0f; }
+    static __device__ __forceinline__ float f(float acc, float m, float x) { return __builtin_fmaf(acc, m, x); }
+};
+template <> struct SegStep<SWS_OP_MAX> {
+    static __device__ __forceinline__ float mask(bool start)
+    {
+        return start ? -__builtin_huge_valf() : __builtin_huge_valf();
+    }
+    static __device__ __forceinline__ float f(float acc, float m, float x)
+    {
+        return __builtin_fmaxf(__builtin_fminf(acc, m), x);
+    }
+};
+template <> struct SegStep<SWS_OP_MIN> {
+    static __device__ __forceinline__ float mask(bool start)
+    {
+        return start ? __builtin_huge_valf() : -__builtin_huge_valf();
+    }
+    static __device__ __forceinline__ float f(float acc, float m, float x)
+    {
+        return __builtin_fminf(__builtin_fmaxf(acc, m), x);
+    }
+};
 
 template <int OP, int C>
 __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__restrict__ x,
                                                               float *__restrict__ y, int len, int lo, int S,
                                                               float scale, int tiles_per_row, int tout,
-                                                              int group, int chunks_per_row,
-                                                              int64_t n_units)
+                                                              int group, int64_t n_tiles, int64_t n_units,
+                                                              int flags)
 {
     using O = Op<OP>;
+    using G = SegStep<OP>;
     static_assert(C == 16, "the LDS layout assumes 16-element chunks");
     constexpr int N = kWave * C;                    // inputs per wave tile
     constexpr int NS = C / 4;                       // 256-element strips per tile
-    constexpr int REGION = N + N / 4;               // padded floats per LDS array
+    constexpr int REGION = N;
     __shared__ __attribute__((aligned(16))) float lds[kWavesPerWg * 2 * REGION];
 
-    const int64_t unit = xcd_unit(n_units);
+    // kernel flag bits: 2 = non-temporal stores, 4 = aligned tile origins, 32 = workgroups keep
+    // their launch order instead of the XCD-contiguous mapping
+    const int64_t unit = (flags & 32) ? (int64_t)blockIdx.x : xcd_unit(n_units);
     if (unit < 0) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    float *A = lds + wave * 2 * REGION;             // staged inputs, later Pre
-    float *Bf = A + REGION;                         // Suf
-    const int64_t r = unit / chunks_per_row;
-    const int chunk = (int)(unit - r * chunks_per_row);
-    const float *xr = x + r * (int64_t)len;
-    float *yr = y + r * (int64_t)lo;
-    int t_end = (chunk + 1) * group;
-    if (t_end > tiles_per_row) t_end = tiles_per_row;
+    float *Bf = lds + wave * 2 * REGION;            // Suf
+    float *A = Bf + REGION;                         // staged inputs, later Pre
+    // Tiles are numbered over all rows (row-major) and dealt out in groups of `group`
+    // consecutive tiles per workgroup, wavefront w taking every fourth: equal work per
+    // wavefront whatever the row length.
+    int64_t gt = unit * group + wave;
+    int64_t gt_end = (unit + 1) * group;
+    if (gt_end > n_tiles) gt_end = n_tiles;
+    int64_t r = gt / tiles_per_row;
+    int t = (int)(gt - r * tiles_per_row);
+    const bool aligned = (flags & 4) != 0;          // tile origins on 64-byte boundaries of y
 
-    // Lane constants.  This lane scans local positions C*lane .. C*lane+C-1; isb[k] says a
-    // segment starts at element k (k = C: at the first element of the next lane).
+    // Lane constants.  This lane scans local positions C*lane .. C*lane+C-1; m[k] is the reset
+    // mask of element k: a segment (S elements, counted from the tile origin) starts there.
+    // m[C] belongs to the first element of the next lane.
     const int q0 = (C * lane) % S;
-    bool isb[C + 1];
+    float m[C + 1];
     {
         int q = q0;
 #pragma unroll
         for (int k = 0; k <= C; ++k) {
-            isb[k] = (q == 0);
+            m[k] = G::mask(q == 0);
             q = (q + 1 == S) ? 0 : q + 1;
         }
     }
@@ -172,26 +214,33 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
     const int n_suf = (rem + C - 1) / C;            // later lanes holding them
     const int max_reach = (S - 1 + C - 1) / C;
     const int sh = S & 3;                           // misalignment of Pre[q+S] against strips
+    const int chunk_pos = lds_pos(C * lane);        // my chunk: group u of it sits at chunk_pos ^ (4*u)
 
-    for (int t = chunk * group + wave; t < t_end; t += kWavesPerWg) {
-        const int t0 = t * tout;
-        // ---- stage the tile: coalesced strips -> LDS
-        if (t0 <= len - N) {
+    for (; gt < gt_end; gt += kWavesPerWg) {
+        const float *xr = x + r * (int64_t)len;
+        float *yr = y + r * (int64_t)lo;
+        // With aligned tiles the origin is pulled back so that (r*lo + t0) is a multiple of 16
+        // floats: every 1 KB strip store then starts on a 64-byte line.  The first tile of a row
+        // may start before the row (t0 < 0); those outputs are not stored.
+        const int t0 = t * tout - (aligned ? (int)((r * lo) & 15) : 0);
+        const int qlo = t0 < 0 ? -t0 : 0;
+        // ---- stage the tile: coalesced strips -> LDS, identity outside the row
+        if (t0 >= 0 && t0 <= len - N) {
 #pragma unroll
             for (int j = 0; j < NS; ++j) {
                 const int q = j * 256 + 4 * lane;
-                const v4f g = __builtin_nontemporal_load((const v4f_u *)(xr + t0 + q));
-                *(v4f *)(A + lds_pos(q)) = g;
+                *(v4f *)(A + lds_pos(q)) = *(const v4f_u *)(xr + t0 + q);
             }
         } else {
 #pragma unroll
             for (int j = 0; j < NS; ++j) {
                 const int q = j * 256 + 4 * lane;
                 v4f g;
-                g.x = (t0 + q + 0 < len) ? xr[t0 + q + 0] : O::id();
-                g.y = (t0 + q + 1 < len) ? xr[t0 + q + 1] : O::id();
-                g.z = (t0 + q + 2 < len) ? xr[t0 + q + 2] : O::id();
-                g.w = (t0 + q + 3 < len) ? xr[t0 + q + 3] : O::id();
+                const int p = t0 + q;
+                g.x = (p + 0 >= 0 && p + 0 < len) ? xr[p + 0] : O::id();
+                g.y = (p + 1 >= 0 && p + 1 < len) ? xr[p + 1] : O::id();
+                g.z = (p + 2 >= 0 && p + 2 < len) ? xr[p + 2] : O::id();
+                g.w = (p + 3 >= 0 && p + 3 < len) ? xr[p + 3] : O::id();
                 *(v4f *)(A + lds_pos(q)) = g;
             }
         }
@@ -200,22 +249,16 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
         float v[C];
 #pragma unroll
         for (int u = 0; u < NS; ++u) {
-            const v4f g = *(const v4f *)(A + lds_pos(C * lane) + 4 * u);
+            const v4f g = *(const v4f *)(A + (chunk_pos ^ (4 * u)));
             v[4 * u] = g.x; v[4 * u + 1] = g.y; v[4 * u + 2] = g.z; v[4 * u + 3] = g.w;
         }
-        // ---- pass 1: lane totals.  tail = my last segment's part inside the chunk,
-        //      head = my first segment's part inside the chunk.
-        float tail, head;
-        {
-            float p[C];
-            p[0] = v[0];
+        // ---- pass 1: lane totals.  tail = my last segment's part inside the chunk (end of a
+        //      forward scan), head = my first segment's part (end of a backward scan).
+        float tail = v[0], head = v[C - 1];
 #pragma unroll
-            for (int k = 1; k < C; ++k) p[k] = isb[k] ? v[k] : O::f(p[k - 1], v[k]);
-            tail = p[C - 1];
-            head = p[C - 1];
+        for (int k = 1; k < C; ++k) tail = G::f(tail, m[k], v[k]);
 #pragma unroll
-            for (int k = C - 2; k >= 0; --k) head = isb[k + 1] ? p[k] : head;
-        }
+        for (int k = C - 2; k >= 0; --k) head = G::f(head, m[k + 1], v[k]);
         // ---- cross-lane: e = (+) of the tails of the n_pre lanes before me,
         //                  g = (+) of the heads of the n_suf lanes after me.
         float e = lane_read(tail, lane - 1);
@@ -226,26 +269,25 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
             if (n_pre > d) e = O::f(te, e);
             if (n_suf > d) g = O::f(g, tg);
         }
-        // ---- pass 2: seeded scans give the final in-segment prefix and suffix sums
-        float pre[C], suf[C];
-        pre[0] = isb[0] ? v[0] : O::f(e, v[0]);
+        // ---- pass 2: the same scans seeded with the carries give the final in-segment
+        //      prefix sums (in place over v) and suffix sums
+        float suf[C];
+        suf[C - 1] = G::f(g, m[C], v[C - 1]);
 #pragma unroll
-        for (int k = 1; k < C; ++k) pre[k] = isb[k] ? v[k] : O::f(pre[k - 1], v[k]);
-        suf[C - 1] = isb[C] ? v[C - 1] : O::f(v[C - 1], g);
+        for (int k = C - 2; k >= 0; --k) suf[k] = G::f(suf[k + 1], m[k + 1], v[k]);
+        v[0] = G::f(e, m[0], v[0]);
 #pragma unroll
-        for (int k = C - 2; k >= 0; --k) suf[k] = isb[k + 1] ? v[k] : O::f(v[k], suf[k + 1]);
+        for (int k = 1; k < C; ++k) v[k] = G::f(v[k - 1], m[k], v[k]);
         // ---- chunks -> LDS (Pre over the staged inputs, Suf beside it)
 #pragma unroll
         for (int u = 0; u < NS; ++u) {
-            const v4f gp = {pre[4 * u], pre[4 * u + 1], pre[4 * u + 2], pre[4 * u + 3]};
-            const v4f gs = {suf[4 * u], suf[4 * u + 1], suf[4 * u + 2], suf[4 * u + 3]};
-            *(v4f *)(A + lds_pos(C * lane) + 4 * u) = gp;
-            *(v4f *)(Bf + lds_pos(C * lane) + 4 * u) = gs;
+            *(v4f *)(A + (chunk_pos ^ (4 * u))) = (v4f){v[4 * u], v[4 * u + 1], v[4 * u + 2], v[4 * u + 3]};
+            *(v4f *)(Bf + (chunk_pos ^ (4 * u))) = (v4f){suf[4 * u], suf[4 * u + 1], suf[4 * u + 2], suf[4 * u + 3]};
         }
         wave_lds_sync();
         // ---- combine on strips: y[q] = Suf[q] (+) Pre[q+S], then coalesced stores
         int lim = lo - t0;
-        if (lim > tout) lim = tout;
+        if (lim > tout) lim = tout;                              // (a tile past the row end has lim <= 0)
 #pragma unroll
         for (int j = 0; j < NS; ++j) {
             const int q = j * 256 + 4 * lane;
@@ -253,7 +295,7 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
             const v4f s4 = *(const v4f *)(Bf + lds_pos(q));
             const int a = q + S - sh;                            // aligned group holding Pre[q+S]
             const v4f p0 = *(const v4f *)(A + lds_pos(a));
-            const v4f p1 = *(const v4f *)(A + lds_pos(a + 4));
+            const v4f p1 = *(const v4f *)(A + lds_pos(a + 4 < N ? a + 4 : a));   // past N: discarded lanes only
             v4f pn;
             switch (sh) {
             case 0: pn = p0; break;
@@ -264,15 +306,19 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
             v4f o;
             o.x = O::f(s4.x, pn.x); o.y = O::f(s4.y, pn.y); o.z = O::f(s4.z, pn.z); o.w = O::f(s4.w, pn.w);
             if (OP == SWS_OP_ADD) o *= scale;
-            if (q + 4 <= lim) {
-                __builtin_nontemporal_store(o, (v4f_u *)(yr + t0 + q));
+            if (q >= qlo && q + 4 <= lim) {
+                if (flags & 2) __builtin_nontemporal_store(o, (v4f_u *)(yr + t0 + q));
+                else *(v4f_u *)(yr + t0 + q) = o;
             } else {
-                if (q + 0 < lim) yr[t0 + q + 0] = o.x;
-                if (q + 1 < lim) yr[t0 + q + 1] = o.y;
-                if (q + 2 < lim) yr[t0 + q + 2] = o.z;
+                if (q + 0 >= qlo && q + 0 < lim) yr[t0 + q + 0] = o.x;
+                if (q + 1 >= qlo && q + 1 < lim) yr[t0 + q + 1] = o.y;
+                if (q + 2 >= qlo && q + 2 < lim) yr[t0 + q + 2] = o.z;
+                if (q + 3 >= qlo && q + 3 < lim) yr[t0 + q + 3] = o.w;
             }
         }
         wave_lds_sync();                                         // the next tile overwrites A
+        t += kWavesPerWg;
+        while (t >= tiles_per_row) { t -= tiles_per_row; ++r; }
     }
 }
 
@@ -297,17 +343,46 @@ hipError_t launch_direct(const float *x, float *y, int64_t rows, int len, int lo
     return hipGetLastError();
 }
 
+// slide_chunk option bits (A/B measurements): 1 = never align tiles, 2 = plain instead of
+// non-temporal stores on aligned tiles, 4 = force the XCD-contiguous unit mapping on,
+// 8 = force it off.
 template <int OP>
 hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, int w, float scale,
                        hipStream_t s)
 {
     constexpr int C = 16, N = kWave * C;
     const int S = w - 1;
-    const TilePlan p = plan_tiles(rows, lo, N - S);
-    const int64_t grid = xcd_grid(p.n_units);
+    const int max_tout = N - S;
+    const int opt = g_opt.slide_chunk;
+    int flags = 0;
+    // Unaligned plan: as few tiles per row as possible.  Aligned plan (preferred; measured
+    // faster even when it costs one more tile per row): tile length a multiple of 16 floats and
+    // origins pulled back per row so that every strip store starts on a 64-byte line of y,
+    // which also makes non-temporal stores pay off.
+    int tiles = (lo + max_tout - 1) / max_tout;
+    int tout = (lo + tiles - 1) / tiles;
+    if (!(opt & 1) && max_tout >= 16) {
+        tout = max_tout & ~15;
+        tiles = (lo + 15 + tout - 1) / tout;
+        flags |= 4;
+        if (!(opt & 2)) flags |= 2;
+    }
+    // Few tiles per workgroup and many workgroups: the set of tiles in flight then stays a
+    // compact window sweeping through memory.  Measured on 2 GiB inputs: one tile per wavefront
+    // is best while the halo is small; with a large halo two tiles per wavefront and plain
+    // round-robin placement of workgroups over the XCDs win.
+    const int64_t n_tiles = rows * tiles;
+    int64_t g = (S <= 64) ? kWavesPerWg : 2 * kWavesPerWg;
+    bool remap = S <= 64;
+    if (g_opt.slide_group > 0) g = (g_opt.slide_group + kWavesPerWg - 1) / kWavesPerWg * kWavesPerWg;
+    if (opt & 4) remap = true;
+    if (opt & 8) remap = false;
+    if (!remap) flags |= 32;
+    const int64_t n_units = (n_tiles + g - 1) / g;
+    const int64_t grid = remap ? xcd_grid(n_units) : n_units;
     if (grid > 2147483647LL) return hipErrorInvalidValue;
     hipLaunchKernelGGL((slide_scan_kernel<OP, C>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
-                       S, scale, p.tiles_per_row, p.tout, p.group, p.chunks_per_row, p.n_units);
+                       S, scale, tiles, tout, (int)g, n_tiles, n_units, flags);
     return hipGetLastError();
 }
 
@@ -323,7 +398,7 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
     int variant = g_opt.slide_variant;
     if (variant == 2 && w > kDirectMaxW) variant = 0;
     if (variant == 3 && (w < 2 || w > kScanMaxW)) variant = 0;
-    if (variant == 0) variant = (w <= 8) ? 2 : (w <= kScanMaxW ? 3 : 1);
+    if (variant == 0) variant = (w == 1) ? 2 : (w <= kScanMaxW ? 3 : 1);
     if (variant == 1) return launch_slide1d_naive(op, x, y, rows, len64, w, scale, s);
     if (variant == 2) {
         switch (op) {

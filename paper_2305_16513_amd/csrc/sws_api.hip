@@ -4,7 +4,7 @@
 #include "sws_internal.h"
 
 namespace sws {
-Options g_opt = {0, 0, 0, 0, 0, 0};
+Options g_opt = {0, 0, 0, 0, 0, 0, 0};
 }
 
 namespace {
@@ -56,6 +56,7 @@ sws_status sws_set_option(const char *key, int64_t value)
     const int v = (int)value;
     if (!strcmp(key, "slide_variant")) sws::g_opt.slide_variant = v;
     else if (!strcmp(key, "slide_chunk")) sws::g_opt.slide_chunk = v;
+    else if (!strcmp(key, "slide_group")) sws::g_opt.slide_group = v;
     else if (!strcmp(key, "pool2d_variant")) sws::g_opt.pool2d_variant = v;
     else if (!strcmp(key, "conv1d_variant")) sws::g_opt.conv1d_variant = v;
     else if (!strcmp(key, "conv2d_variant")) sws::g_opt.conv2d_variant = v;

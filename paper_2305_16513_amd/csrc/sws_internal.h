@@ -11,6 +11,7 @@ namespace sws {
 struct Options {
     int slide_variant;
     int slide_chunk;
+    int slide_group;
     int pool2d_variant;
     int conv1d_variant;
     int conv2d_variant;
@@ -34,11 +35,11 @@ template <> struct Op<SWS_OP_ADD> {
 };
 template <> struct Op<SWS_OP_MAX> {
     static __device__ __forceinline__ float id() { return -__builtin_huge_valf(); }
-    static __device__ __forceinline__ float f(float a, float b) { return a < b ? b : a; }
+    static __device__ __forceinline__ float f(float a, float b) { return __builtin_fmaxf(a, b); }
 };
 template <> struct Op<SWS_OP_MIN> {
     static __device__ __forceinline__ float id() { return __builtin_huge_valf(); }
-    static __device__ __forceinline__ float f(float a, float b) { return b < a ? b : a; }
+    static __device__ __forceinline__ float f(float a, float b) { return __builtin_fminf(a, b); }
 };
 
 // Workgroups are dealt round-robin to the 8 XCDs.  This maps blockIdx so that each XCD
