@@ -27,9 +27,14 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Position q of a wave tile lives at q + 4*(q/16): 16-byte aligned for strips (q = 4*lane)
-// and for per-lane windows (q = 16*lane + 4*u), and both shapes spread over the banks.
-__host__ __device__ constexpr int lds_pos(int q) { return q + ((q >> 4) << 2); }
+// LDS layout of a wave tile: rows of 64 floats (16 groups of 4); group c of row r is stored at
+// group (c ^ (r & 3)).  Strips (16 consecutive lanes = one row) and per-lane windows (lane l
+// reads groups 4*l + u; 16 lanes span 4 rows whose group sets the XOR makes disjoint) both
+// touch all 64 banks exactly once per 16 lanes of a 128-bit access.
+__host__ __device__ constexpr int lds_pos(int q)
+{
+    return (q & ~63) | (((((q >> 2) & 15) ^ ((q >> 6) & 3))) << 2) | (q & 3);
+}
 
 template <int KB4>
 __global__ __launch_bounds__(kThreads) void conv1d_thin_kernel(
@@ -38,7 +43,8 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_kernel(
 {
     constexpr int K4 = 4 * KB4;                      // taps, zero-padded to a multiple of 4
     constexpr int NI = kTileOut + K4;                // staged inputs per tile
-    constexpr int REGION = lds_pos(NI + 15);
+    constexpr int NG = KB4 + 4;                      // 4-float groups in a lane's window
+    constexpr int REGION = (NI + 63) / 64 * 64;
     __shared__ __attribute__((aligned(16))) float lds[kWavesPerWg * REGION];
 
     const int64_t unit = xcd_unit(n_units);
@@ -53,47 +59,57 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_kernel(
     const float *xr = x + (b * Cin + co / cog) * (int64_t)L;
     const float *wr = wgt + (int64_t)co * k;
     float *yr = y + ro * (int64_t)Lo;
+    // Tile origins are pulled back by c so that (ro*Lo + t0) is a multiple of 16 floats: every
+    // 1 KB strip store starts on a 64-byte line of y.  Outputs before the row start are dropped.
+    const int c = (int)((ro * Lo) & 15);
 
     float f[K4];
 #pragma unroll
     for (int t = 0; t < K4; ++t) f[t] = (t < k) ? wr[t] : 0.0f;
 
-    int t_end = (chunk + 1) * group;
-    if (t_end > tiles_per_row) t_end = tiles_per_row;
-    for (int t = chunk * group + wave; t < t_end; t += kWavesPerWg) {
-        const int t0 = t * kTileOut;                 // first output of the tile
-        const int p0 = t0 - pad;                     // input position of staged element 0
-        // ---- stage inputs [p0, p0 + NI): four strips plus the k-1 halo
+    int wpos[NG];                                    // LDS offsets of my window's groups
+#pragma unroll
+    for (int u = 0; u < NG; ++u) wpos[u] = lds_pos(16 * lane + 4 * u);
+
+    // Strips of one tile (inputs [p0, p0 + NI)): 4 full strips plus the k-1 halo, zero outside the row.
+    auto load_tile = [&](int t, v4f (&g)[5]) {
+        const int p0 = t * kTileOut - c - pad;
         if (p0 >= 0 && p0 <= L - NI) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int q = j * 256 + 4 * lane;
-                *(v4f *)(A + lds_pos(q)) = __builtin_nontemporal_load((const v4f_u *)(xr + p0 + q));
-            }
-            if (4 * lane < K4) {
-                const int q = kTileOut + 4 * lane;
-                *(v4f *)(A + lds_pos(q)) = *(const v4f_u *)(xr + p0 + q);
-            }
+            for (int j = 0; j < 4; ++j) g[j] = *(const v4f_u *)(xr + p0 + j * 256 + 4 * lane);
+            g[4] = (4 * lane < K4) ? *(const v4f_u *)(xr + p0 + kTileOut + 4 * lane) : (v4f){0.0f, 0.0f, 0.0f, 0.0f};
         } else {
 #pragma unroll
             for (int j = 0; j < 5; ++j) {
-                const int q = j * 256 + 4 * lane;
-                if (q < NI) {
-                    v4f g;
-                    g.x = (p0 + q + 0 >= 0 && p0 + q + 0 < L) ? xr[p0 + q + 0] : 0.0f;
-                    g.y = (p0 + q + 1 >= 0 && p0 + q + 1 < L) ? xr[p0 + q + 1] : 0.0f;
-                    g.z = (p0 + q + 2 >= 0 && p0 + q + 2 < L) ? xr[p0 + q + 2] : 0.0f;
-                    g.w = (p0 + q + 3 >= 0 && p0 + q + 3 < L) ? xr[p0 + q + 3] : 0.0f;
-                    *(v4f *)(A + lds_pos(q)) = g;
-                }
+                const int p = p0 + j * 256 + 4 * lane;
+                g[j].x = (p + 0 >= 0 && p + 0 < L) ? xr[p + 0] : 0.0f;
+                g[j].y = (p + 1 >= 0 && p + 1 < L) ? xr[p + 1] : 0.0f;
+                g[j].z = (p + 2 >= 0 && p + 2 < L) ? xr[p + 2] : 0.0f;
+                g[j].w = (p + 3 >= 0 && p + 3 < L) ? xr[p + 3] : 0.0f;
             }
         }
+    };
+
+    int t_end = (chunk + 1) * group;
+    if (t_end > tiles_per_row) t_end = tiles_per_row;
+    int t = chunk * group + wave;
+    v4f cur[5];
+    if (t < t_end) load_tile(t, cur);
+    for (; t < t_end; t += kWavesPerWg) {
+        const int t0 = t * kTileOut - c;             // first output of the tile (may be < 0 for t = 0)
+        // ---- the next tile's loads go out before this tile's arithmetic
+        v4f nxt[5];
+        if (t + kWavesPerWg < t_end) load_tile(t + kWavesPerWg, nxt);
+        // ---- stage: strips -> LDS
+#pragma unroll
+        for (int j = 0; j < 4; ++j) *(v4f *)(A + lds_pos(j * 256 + 4 * lane)) = cur[j];
+        if (4 * lane < K4) *(v4f *)(A + lds_pos(kTileOut + 4 * lane)) = cur[4];
         wave_lds_sync();
         // ---- my window: inputs 16*lane .. 16*lane + K4 + 15
         float xw[K4 + 16];
 #pragma unroll
-        for (int u = 0; u < KB4 + 4; ++u) {
-            const v4f g = *(const v4f *)(A + lds_pos(16 * lane) + lds_pos(4 * u));
+        for (int u = 0; u < NG; ++u) {
+            const v4f g = *(const v4f *)(A + wpos[u]);
             xw[4 * u] = g.x; xw[4 * u + 1] = g.y; xw[4 * u + 2] = g.z; xw[4 * u + 3] = g.w;
         }
         // ---- slide the taps: acc[e] = sum_t f[t] * x[e + t]
@@ -108,24 +124,27 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_kernel(
         // ---- per-lane outputs -> strips
 #pragma unroll
         for (int u = 0; u < 4; ++u)
-            *(v4f *)(A + lds_pos(16 * lane) + 4 * u) =
-                (v4f){acc[4 * u], acc[4 * u + 1], acc[4 * u + 2], acc[4 * u + 3]};
+            *(v4f *)(A + wpos[u]) = (v4f){acc[4 * u], acc[4 * u + 1], acc[4 * u + 2], acc[4 * u + 3]};
         wave_lds_sync();
         const int lim = Lo - t0;
+        const int qlo = t0 < 0 ? -t0 : 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int q = j * 256 + 4 * lane;
             if (q >= lim) continue;
             const v4f o = *(const v4f *)(A + lds_pos(q));
-            if (q + 4 <= lim) {
+            if (q >= qlo && q + 4 <= lim) {
                 __builtin_nontemporal_store(o, (v4f_u *)(yr + t0 + q));
             } else {
-                yr[t0 + q] = o.x;
-                if (q + 1 < lim) yr[t0 + q + 1] = o.y;
-                if (q + 2 < lim) yr[t0 + q + 2] = o.z;
+                if (q + 0 >= qlo && q + 0 < lim) yr[t0 + q + 0] = o.x;
+                if (q + 1 >= qlo && q + 1 < lim) yr[t0 + q + 1] = o.y;
+                if (q + 2 >= qlo && q + 2 < lim) yr[t0 + q + 2] = o.z;
+                if (q + 3 >= qlo && q + 3 < lim) yr[t0 + q + 3] = o.w;
             }
         }
         wave_lds_sync();
+#pragma unroll
+        for (int j = 0; j < 5; ++j) cur[j] = nxt[j];
     }
 }
 
@@ -133,9 +152,9 @@ template <int KB4>
 hipError_t launch_thin(const float *x, const float *wgt, float *y, int64_t rows_out, int L, int Lo, int k, int pad,
                        int Cin, int Cout, int cog, hipStream_t s)
 {
-    const int tiles_per_row = (Lo + kTileOut - 1) / kTileOut;
-    int64_t g = rows_out * tiles_per_row / 2048;
-    if (g < kWavesPerWg) g = kWavesPerWg;
+    const int tiles_per_row = (Lo + 15 + kTileOut - 1) / kTileOut;     // origins move back by up to 15
+    int64_t g = 4 * kWavesPerWg;                   // taps are loaded once per workgroup: keep a few tiles each
+    if (g_opt.slide_group > 0) g = g_opt.slide_group;
     if (g > tiles_per_row) g = tiles_per_row;
     const int group = (int)g;
     const int chunks_per_row = (tiles_per_row + group - 1) / group;
