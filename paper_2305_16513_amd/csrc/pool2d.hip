@@ -2,12 +2,14 @@
 // dimensions): first the sliding sum down H, then the sliding sum along W, both on a
 // tile that stays on chip, so HBM sees one read of x and one write of y.
 //
-// A workgroup stages a band of input rows of one plane in LDS with coalesced 128-bit
-// loads (the band is one contiguous range of the plane).  A lane then owns four adjacent
-// output columns and R consecutive output rows: it reads the (R-1)*SH+KH input rows of
-// its column window once, combines them down H (each input row is shared by up to KH
-// output rows), then slides the KW-window along W in registers.  Cells outside the plane
-// hold the identity of the operator.
+// A wavefront stages a band of input rows of one plane in its own LDS slice with coalesced
+// 128-bit loads (the band is one contiguous range of the plane); there is no workgroup
+// barrier, the four wavefronts of a workgroup work on four consecutive bands.  A lane then
+// owns four adjacent output columns and R consecutive output rows: it reads the
+// (R-1)*SH+KH input rows of its column window once, combines them down H (each input row is
+// shared by up to KH output rows), then slides the KW-window along W in registers.  Cells
+// outside the plane hold the identity of the operator.  Bands are small (a few KB in, a few KB
+// out per wavefront) so that the tiles in flight form a compact window sweeping through memory.
 #include "sws_internal.h"
 
 namespace sws {
@@ -15,25 +17,42 @@ namespace sws {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kRowsPerItem = 4;                      // R: consecutive output rows per lane
-constexpr int kLdsBudget = 24 * 1024;                // bytes of LDS per workgroup
+constexpr int kWaves = kThreads / kWave;
+constexpr int kLdsBudget = 8 * 1024;                 // bytes of LDS per wavefront
+
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// R = consecutive output rows per lane: 4 at stride 1 (each staged row feeds up to KH of them);
+// 1 at larger strides, where rows overlap little and consecutive lanes then store one
+// contiguous run of y.
+template <int SH> struct RowsPerItem { static constexpr int value = (SH == 1) ? 4 : 1; };
 
 template <int OP, int KH, int KW, int SH, int SW, int PW>
 __global__ __launch_bounds__(kThreads) void pool2d_band_kernel(
     const float *__restrict__ x, float *__restrict__ y, int H, int W, int Ho, int Wo, int ph, int P, int TH,
-    int bands, float scale, int64_t n_units)
+    int bands, float scale, int64_t n_units, int lds_floats, int flags)
 {
     using O = Op<OP>;
-    constexpr int R = kRowsPerItem;
+    constexpr int R = RowsPerItem<SH>::value;
     constexpr int NR = (R - 1) * SH + KH;            // input rows per item
     constexpr int LPAD = (PW + 3) / 4 * 4;           // aligned columns read left of the window
     constexpr int OFF = LPAD - PW;                   // window start inside the aligned read
     constexpr int NC = 3 * SW + KW;                  // input columns per item
     constexpr int NG = (OFF + NC + 3) / 4;           // aligned 4-column groups per input row
-    extern __shared__ __attribute__((aligned(16))) float lds[];
+    extern __shared__ __attribute__((aligned(16))) float lds_all[];
 
-    const int64_t unit = xcd_unit(n_units);
-    if (unit < 0) return;
+    // flag bits: 2 = XCD-contiguous placement of workgroups (default: launch order), 4 = plain stores
+    const int64_t wg = (flags & 2) ? xcd_unit((n_units + kWaves - 1) / kWaves) : (int64_t)blockIdx.x;
+    if (wg < 0) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t unit = wg * kWaves + wave;          // one band per wavefront
+    if (unit >= n_units) return;
+    float *lds = lds_all + wave * lds_floats;
     const int64_t plane = unit / bands;
     const int band = (int)(unit - plane * bands);
     const float *xp = x + plane * (int64_t)H * W;
@@ -48,23 +67,35 @@ __global__ __launch_bounds__(kThreads) void pool2d_band_kernel(
 
     // ---- stage the band
     if (P == W) {
+        // the band is one contiguous range: all its 128-bit loads are issued before the first
+        // LDS write (lanes past the end re-read element 0 and drop it)
         const float *src = xp + (int64_t)row_lo * W;
-        const int n = (row_hi - row_lo) * W;         // multiple of 4
-        for (int i = 4 * threadIdx.x; i < n; i += 4 * kThreads)
-            *(v4f *)(lds + i) = *(const v4f_u *)(src + i);
+        const int n = (row_hi - row_lo) * W;         // multiple of 4, at most kLdsBudget / 4
+        constexpr int NL = kLdsBudget / 16 / kWave;
+        v4f g[NL];
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            const int i = 4 * (lane + kWave * j);
+            g[j] = *(const v4f_u *)(src + (i < n ? i : 0));
+        }
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            const int i = 4 * (lane + kWave * j);
+            if (i < n) *(v4f *)(lds + i) = g[j];
+        }
     } else {
         const int n = (row_hi - row_lo) * P;
-        for (int i = threadIdx.x; i < n; i += kThreads) {
+        for (int i = lane; i < n; i += kWave) {
             const int r = i / P, c = i - r * P;
             lds[i] = (c < W) ? xp[(int64_t)(row_lo + r) * W + c] : O::id();
         }
     }
-    __syncthreads();
+    wave_lds_sync();
 
     // ---- items: (row block, column group), column group fastest
     const int CG = (Wo + 3) / 4;
     const int RB = (ho1 - ho0 + R - 1) / R;
-    for (int item = threadIdx.x; item < CG * RB; item += kThreads) {
+    for (int item = lane; item < CG * RB; item += kWave) {
         const int rb = item / CG, cg = item - rb * CG;
         const int ho = ho0 + rb * R;
         const int hin0 = ho * SH - ph;               // first input row of the item
@@ -105,7 +136,8 @@ __global__ __launch_bounds__(kThreads) void pool2d_band_kernel(
             }
             float *dst = yp + (int64_t)(ho + ro) * Wo + 4 * cg;
             if (4 * cg + 4 <= Wo) {
-                __builtin_nontemporal_store((v4f){o[0], o[1], o[2], o[3]}, (v4f_u *)dst);
+                if (flags & 4) *(v4f_u *)dst = (v4f){o[0], o[1], o[2], o[3]};
+                else __builtin_nontemporal_store((v4f){o[0], o[1], o[2], o[3]}, (v4f_u *)dst);
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
@@ -116,27 +148,28 @@ __global__ __launch_bounds__(kThreads) void pool2d_band_kernel(
 }
 
 struct BandPlan {
-    int P, TH, bands;
+    int P, TH, bands, threads;
     size_t lds_bytes;
     bool ok;
 };
 
-BandPlan plan_bands(int W, int Ho, int KH, int SH)
+BandPlan plan_bands(int W, int Ho, int Wo, int KH, int SH, int R)
 {
     BandPlan p;
     p.P = (W + 3) / 4 * 4;
-    const int R = kRowsPerItem;
-    const int max_rows = kLdsBudget / (4 * p.P);                 // input rows that fit
-    int th = (max_rows - KH) / SH + 1;                           // output rows they feed
+    // Aim for about 4.5 KB of staged input per wavefront (measured best on 112x112 planes: 10
+    // input rows, i.e. 8 output rows at stride 1 and 4 at stride 2), never more than the slice.
+    const int want_rows = 4608 / (4 * p.P);
+    int th = (want_rows - KH) / SH + 1;
+    if (g_opt.slide_group > 0) th = g_opt.slide_group;
     th = th / R * R;
-    p.ok = th >= R;
-    if (!p.ok) return p;
-    // never more than the plane has, and balance the bands
-    const int bands = (Ho + th - 1) / th;
-    th = ((Ho + bands - 1) / bands + R - 1) / R * R;
+    if (th < R) th = R;
+    if (th > (Ho + R - 1) / R * R) th = (Ho + R - 1) / R * R;
     p.TH = th;
     p.bands = (Ho + th - 1) / th;
     p.lds_bytes = (size_t)((th - 1) * SH + KH) * p.P * 4;
+    p.ok = p.lds_bytes <= (size_t)kLdsBudget;
+    p.threads = kThreads;
     return p;
 }
 
@@ -144,14 +177,17 @@ template <int OP, int KH, int KW, int SH, int SW, int PW>
 hipError_t launch_band(const float *x, float *y, int64_t planes, int H, int W, int Ho, int Wo, int ph, float scale,
                        hipStream_t s, bool *taken)
 {
-    const BandPlan p = plan_bands(W, Ho, KH, SH);
+    const BandPlan p = plan_bands(W, Ho, Wo, KH, SH, RowsPerItem<SH>::value);
     *taken = p.ok;
     if (!p.ok) return hipSuccess;
     const int64_t n_units = planes * p.bands;
-    const int64_t grid = xcd_grid(n_units);
+    const int flags = g_opt.pool2d_variant;
+    const int64_t n_wg = (n_units + kWaves - 1) / kWaves;
+    const int64_t grid = (flags & 2) ? xcd_grid(n_wg) : n_wg;
     if (grid > 2147483647LL) { *taken = false; return hipSuccess; }
     hipLaunchKernelGGL((pool2d_band_kernel<OP, KH, KW, SH, SW, PW>), dim3((unsigned)grid), dim3(kThreads),
-                       p.lds_bytes, s, x, y, H, W, Ho, Wo, ph, p.P, p.TH, p.bands, scale, n_units);
+                       p.lds_bytes * kWaves, s, x, y, H, W, Ho, Wo, ph, p.P, p.TH, p.bands, scale, n_units,
+                       (int)(p.lds_bytes / 4), flags);
     return hipGetLastError();
 }
 
