@@ -240,6 +240,167 @@ __global__ __launch_bounds__(WAVES * 64, 2) void conv2d_mfma_kernel(const float 
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Channel-fastest variant for kh*kw <= 9: 128-bit operand reads.
+// ------------------------------------------------------------------------------------------
+// Same tiling (64 output channels x 128 positions, 8 wavefronts, one 32x32 accumulator block
+// each) but the LDS tiles keep the 8 input channels of a block next to each other:
+//   Xl[position][12]      (8 channels + 4 floats of padding: pitch 48 bytes)
+//   Wl[tap][channel out][12]
+// The k index of the four MFMA steps of a tap is mapped as step j <-> channels (j, 4+j), so
+// the half-wave h needs channels 4h .. 4h+3 of its position / output channel: ONE 128-bit
+// LDS read per operand feeds four MFMAs (the scalar-read kernel above needs eight reads).
+// With the 12-float pitch sixteen consecutive lanes of a 128-bit read hit sixteen distinct
+// bank quads.
+// Staging plan of the input tile, computed on the host and passed by value: segment i (one
+// staged row of one channel, 64 columns wide) is channel seg_ci[i], row seg_rr[i], chunk
+// seg_ch[i].  Wavefront w moves segments w, w+8, ...; the lookups are scalar loads.
+struct SegPlan {
+    unsigned char ci[64], rr[64], ch[64];
+};
+
+template <int KTT>
+__global__ __launch_bounds__(512, 2) void conv2d_mfma_c8_kernel(const float *__restrict__ x,
+                                                                const float *__restrict__ wgt,
+                                                                float *__restrict__ y, ConvGeom g,
+                                                                SegPlan sp)
+{
+    constexpr int WAVES = 8, CIB = 8, XP = 12;
+    constexpr int XS = 8;                             // staged-input registers per lane (<= 64 segments)
+    constexpr int KTMAX = KTT > 0 ? KTT : 9;          // staged-weight registers per lane
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    float *Xl = lds;
+    float *Wl = lds + g.CP;                           // CP = floats reserved for the input tile here
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+    const int wm = wave & 1, wn = wave >> 1;          // my channel block, my position block
+
+    // grid: x = tile of the image, y = output-channel block, z = image
+    const int tile = blockIdx.x;
+    const int co0 = blockIdx.y * kCoTile;
+    const int64_t n = blockIdx.z;
+    const int KT = KTT > 0 ? KTT : g.kh * g.kw;
+    const int plane = g.H * g.W;
+    const float *xn = x + n * g.Cin * (int64_t)plane;
+
+    int oh_first, ow_first, p_base = 0;
+    if (g.mode_b) {
+        oh_first = tile / g.tiles_c;
+        ow_first = (tile - oh_first * g.tiles_c) * g.NP;
+    } else {
+        p_base = tile * g.NP;
+        oh_first = p_base / g.Wo;
+        ow_first = 0;
+    }
+    const int row0 = oh_first - g.ph, col0 = ow_first - g.pw;
+
+    // my position
+    int oh, ow;
+    bool pok;
+    {
+        const int idx = wn * 32 + l32;
+        if (g.mode_b) {
+            oh = oh_first;
+            ow = ow_first + idx;
+            pok = ow < g.Wo;
+        } else {
+            const int p = p_base + idx;
+            oh = fast_div(p, 1.0f / (float)g.Wo);
+            ow = p - oh * g.Wo;
+            pok = p < g.Ho * g.Wo;
+        }
+    }
+    const int b_lane = (pok ? (oh - oh_first) * g.Wt + (ow - ow_first) : 0) * XP + 4 * half;
+    const int a_lane = (wm * 32 + l32) * XP + 4 * half;
+
+    v16f acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+
+    // ---- input staging plan: slot s of this wavefront moves segment wave + 8*s
+    const int nseg = CIB * g.NRows * g.CH;
+    int xg[XS], xl[XS];
+#pragma unroll
+    for (int s = 0; s < XS; ++s) {
+        const int seg = wave + WAVES * s;
+        const int ci = sp.ci[seg], rr = sp.rr[seg], ch = sp.ch[seg];
+        const int gh = row0 + rr, cc = ch * 64 + lane, gw = col0 + cc;
+        const bool act = seg < nseg && cc < g.Wt;
+        xl[s] = act ? (rr * g.Wt + cc) * XP + ci : -1;
+        xg[s] = (act && gh >= 0 && gh < g.H && gw >= 0 && gw < g.W) ? ci * plane + gh * g.W + gw : -1;
+    }
+    // ---- weight staging plan: thread (co = tid / 8, ci = tid % 8) moves the KT taps of one
+    // (output channel, input channel) pair: KT contiguous floats in memory, and in LDS the
+    // same word of KT consecutive tap planes (a constant stride).
+    const int w_co = threadIdx.x >> 3, w_ci = threadIdx.x & 7;
+    const bool w_ok = co0 + w_co < g.Cout;
+    const float *wsrc = wgt + (w_ok ? ((int64_t)(co0 + w_co) * g.Cin + w_ci) * KT : 0);
+    float *wdst = Wl + w_co * XP + w_ci;
+
+    float xreg[XS], wreg[KTMAX];
+    // Loads are unconditional (out-of-range slots read valid memory and are dropped when the
+    // registers are written to LDS, on the far side of the matrix loop), so nothing forces a
+    // wait on a single load.
+    auto prefetch = [&](int ci0) {
+        const int xb = ci0 * plane;
+#pragma unroll
+        for (int s = 0; s < XS; ++s) xreg[s] = xn[xg[s] >= 0 ? xb + xg[s] : 0];
+        const float *w = wsrc + (w_ok ? ci0 * KT : 0);
+#pragma unroll
+        for (int t = 0; t < KTMAX; ++t) wreg[t] = w[t < KT ? t : 0];
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int s = 0; s < XS; ++s)
+            if (xl[s] >= 0) Xl[xl[s]] = xg[s] >= 0 ? xreg[s] : 0.0f;
+#pragma unroll
+        for (int t = 0; t < KTMAX; ++t)
+            if (t < KT) wdst[t * kCoTile * XP] = w_ok ? wreg[t] : 0.0f;
+    };
+
+    prefetch(0);
+    for (int ci0 = 0; ci0 < g.Cin; ci0 += CIB) {
+        __syncthreads();                              // the previous block has been consumed
+        commit();
+        __syncthreads();
+        if (ci0 + CIB < g.Cin) prefetch(ci0 + CIB);   // in flight during the matrix work below
+        if (KTT > 0) {
+#pragma unroll
+            for (int tap = 0; tap < (KTT > 0 ? KTT : 1); ++tap) {
+                const int shift = (tap / 3) * g.Wt + (tap % 3);          // KTT > 0 is only used with kw == 3
+                const v4f a4 = *(const v4f *)(Wl + tap * kCoTile * XP + a_lane);
+                const v4f b4 = *(const v4f *)(Xl + shift * XP + b_lane);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, b4.x, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.y, b4.y, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.z, b4.z, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, b4.w, acc, 0, 0, 0);
+            }
+        } else {
+            int ta = 0, tb = 0;
+            for (int tap = 0; tap < KT; ++tap) {
+                const int shift = ta * g.Wt + tb;
+                const v4f a4 = *(const v4f *)(Wl + tap * kCoTile * XP + a_lane);
+                const v4f b4 = *(const v4f *)(Xl + shift * XP + b_lane);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, b4.x, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.y, b4.y, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.z, b4.z, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, b4.w, acc, 0, 0, 0);
+                if (++tb == g.kw) { tb = 0; ++ta; }
+            }
+        }
+    }
+
+    if (!pok) return;
+    float *yn = y + n * g.Cout * (int64_t)g.Ho * g.Wo;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int co = co0 + wm * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+        if (co < g.Cout) yn[((int64_t)co * g.Ho + oh) * g.Wo + ow] = acc[v];
+    }
+}
+
 bool plan(ConvGeom &g, int NP, int CIB, int xslots_total, int64_t N, int64_t *n_units, size_t *lds_bytes)
 {
     g.NP = NP;
@@ -298,9 +459,35 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
     g.kh = kh; g.kw = kw; g.ph = ph; g.pw = pw;
     int64_t units = 0;
     size_t lds = 0;
+    // preferred: channel-fastest tiles with 128-bit operand reads (kh*kw <= 9, Cin % 8 == 0)
+    if (KT <= 9 && Cin % 8 == 0 && g_opt.conv2d_variant != 3 && g_opt.conv2d_variant != 4 &&
+        plan(g, 128, 16, 1 << 30, N, &units, &lds)) {
+        const int nseg = 8 * g.NRows * g.CH;
+        const int xfloats = (g.NRows * g.Wt * 12 + 3) / 4 * 4;
+        const size_t lds8 = 4 * ((size_t)xfloats + (size_t)KT * kCoTile * 12);
+        if (nseg <= 64 && g.NRows < 256 && lds8 <= 64 * 1024 && N <= 65535 && g.co_blocks <= 65535) {
+            g.CP = xfloats;
+            SegPlan sp;
+            for (int i = 0; i < 64; ++i) {
+                const int ci = i / (g.NRows * g.CH), r2 = i % (g.NRows * g.CH);
+                sp.ci[i] = (unsigned char)(ci < 8 ? ci : 0);
+                sp.rr[i] = (unsigned char)(r2 / g.CH);
+                sp.ch[i] = (unsigned char)(r2 % g.CH);
+            }
+            const dim3 grid((unsigned)g.tiles_per_img, (unsigned)g.co_blocks, (unsigned)N);
+            *taken = true;
+            if (KT == 9 && kw == 3)
+                hipLaunchKernelGGL((conv2d_mfma_c8_kernel<9>), grid, dim3(512), lds8, s, x, wgt, y, g, sp);
+            else if (KT == 3 && kw == 3)
+                hipLaunchKernelGGL((conv2d_mfma_c8_kernel<3>), grid, dim3(512), lds8, s, x, wgt, y, g, sp);
+            else
+                hipLaunchKernelGGL((conv2d_mfma_c8_kernel<0>), grid, dim3(512), lds8, s, x, wgt, y, g, sp);
+            return hipGetLastError();
+        }
+    }
     if (!plan(g, 128, CIB, CIB == 16 ? 128 : 64, N, &units, &lds)) return hipSuccess;
     *taken = true;
-    if (g_opt.conv2d_variant == 3) {                  // 4 wavefronts, two channel blocks each
+    if (g_opt.conv2d_variant == 3) {                  // 4 wavefronts, two channel blocks each (A/B)
         if (CIB == 16) return launch<4, 2, 1, 16>(x, wgt, y, g, units, lds, s);
         return launch<4, 2, 1, 4>(x, wgt, y, g, units, lds, s);
     }
