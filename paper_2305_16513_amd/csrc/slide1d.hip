@@ -199,9 +199,14 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
     // Lane constants.  This lane scans local positions C*lane .. C*lane+C-1; m[k] is the reset
     // mask of element k: a segment (S elements, counted from the tile origin) starts there.
     // m[C] belongs to the first element of the next lane.
-    const int q0 = (C * lane) % S;
+    const int q0 = (C * lane) - S * (int)(((float)(C * lane) + 0.5f) * (1.0f / (float)S));   // (C*lane) % S
     float m[C + 1];
-    {
+    if (S > C) {
+        // at most one segment start inside k = 0 .. C: at kb = distance to the next multiple of S
+        const int kb = q0 == 0 ? 0 : S - q0;
+#pragma unroll
+        for (int k = 0; k <= C; ++k) m[k] = G::mask(k == kb);
+    } else {
         int q = q0;
 #pragma unroll
         for (int k = 0; k <= C; ++k) {
@@ -215,6 +220,12 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
     const int max_reach = (S - 1 + C - 1) / C;
     const int sh = S & 3;                           // misalignment of Pre[q+S] against strips
     const int chunk_pos = lds_pos(C * lane);        // my chunk: group u of it sits at chunk_pos ^ (4*u)
+    // Strip j of lane l is local position 256*j + 4*l, i.e. group 64*j + l: the swizzle depends
+    // on (group mod 64) only, so one address per lane serves all strips (+256 floats per strip).
+    // The same holds for the two aligned groups that hold Pre[q+S .. q+S+3].
+    const int s4 = (S - sh) >> 2;
+    const int strip_pos = lds_pos(4 * lane);
+    const int pre_pos0 = lds_pos(4 * (lane + s4)), pre_pos1 = lds_pos(4 * (lane + s4 + 1));
 
     for (; gt < gt_end; gt += kWavesPerWg) {
         const float *xr = x + r * (int64_t)len;
@@ -229,7 +240,7 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
 #pragma unroll
             for (int j = 0; j < NS; ++j) {
                 const int q = j * 256 + 4 * lane;
-                *(v4f *)(A + lds_pos(q)) = *(const v4f_u *)(xr + t0 + q);
+                *(v4f *)(A + strip_pos + 256 * j) = *(const v4f_u *)(xr + t0 + q);
             }
         } else {
 #pragma unroll
@@ -241,7 +252,7 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
                 g.y = (p + 1 >= 0 && p + 1 < len) ? xr[p + 1] : O::id();
                 g.z = (p + 2 >= 0 && p + 2 < len) ? xr[p + 2] : O::id();
                 g.w = (p + 3 >= 0 && p + 3 < len) ? xr[p + 3] : O::id();
-                *(v4f *)(A + lds_pos(q)) = g;
+                *(v4f *)(A + strip_pos + 256 * j) = g;
             }
         }
         wave_lds_sync();
@@ -292,10 +303,10 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
         for (int j = 0; j < NS; ++j) {
             const int q = j * 256 + 4 * lane;
             if (q >= lim) continue;
-            const v4f s4 = *(const v4f *)(Bf + lds_pos(q));
-            const int a = q + S - sh;                            // aligned group holding Pre[q+S]
-            const v4f p0 = *(const v4f *)(A + lds_pos(a));
-            const v4f p1 = *(const v4f *)(A + lds_pos(a + 4 < N ? a + 4 : a));   // past N: discarded lanes only
+            const v4f s4v = *(const v4f *)(Bf + strip_pos + 256 * j);
+            // the aligned groups holding Pre[q+S ..]; past the tile (discarded lanes only) wrap around
+            const v4f p0 = *(const v4f *)(A + ((pre_pos0 + 256 * j) & (N - 1)));
+            const v4f p1 = *(const v4f *)(A + ((pre_pos1 + 256 * j) & (N - 1)));
             v4f pn;
             switch (sh) {
             case 0: pn = p0; break;
@@ -304,7 +315,7 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
             default: pn = (v4f){p0.w, p1.x, p1.y, p1.z}; break;
             }
             v4f o;
-            o.x = O::f(s4.x, pn.x); o.y = O::f(s4.y, pn.y); o.z = O::f(s4.z, pn.z); o.w = O::f(s4.w, pn.w);
+            o.x = O::f(s4v.x, pn.x); o.y = O::f(s4v.y, pn.y); o.z = O::f(s4v.z, pn.z); o.w = O::f(s4v.w, pn.w);
             if (OP == SWS_OP_ADD) o *= scale;
             if (q >= qlo && q + 4 <= lim) {
                 if (flags & 2) __builtin_nontemporal_store(o, (v4f_u *)(yr + t0 + q));
