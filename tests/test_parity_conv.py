@@ -95,6 +95,45 @@ def test_conv2d(B, cin, cout, kh, kw, h, w_, geom):
     _c2(B, x, w, sh, sw, ph, pw, what=str((cin, cout, kh, kw, h, w_, geom)))
 
 
+@pytest.mark.parametrize("cin,cout,kh,kw,h,w_,ph,pw", [
+    (12, 20, 3, 3, 21, 25, 1, 1),      # Cin % 8 != 0, % 4 == 0: scalar-read matrix kernel, 4-channel blocks
+    (16, 70, 5, 5, 30, 31, 2, 2),      # 25 taps: scalar-read matrix kernel; Cout not a multiple of 64
+    (32, 64, 1, 7, 9, 300, 0, 3),      # wide rows: column tiles; 7 taps through the generic tap loop
+    (8, 8, 3, 3, 5, 5, 1, 1),          # a single small tile
+    (24, 33, 2, 2, 17, 40, 0, 1),      # even tap count, Cout not a multiple of 32
+    (64, 64, 6, 6, 20, 20, 2, 2),      # 36 taps
+    (64, 64, 7, 7, 20, 20, 3, 3),      # 49 taps: beyond the matrix kernels, direct evaluation
+])
+def test_conv2d_kernel_selection_paths(B, cin, cout, kh, kw, h, w_, ph, pw):
+    r = _rng(cin * 7 + cout + kh * 3 + kw)
+    x = r.standard_normal((3, cin, h, w_), dtype=np.float32)
+    w = (r.standard_normal((cout, cin, kh, kw), dtype=np.float32) * np.sqrt(2.0 / (cin * kh * kw))).astype(np.float32)
+    _c2(B, x, w, 1, 1, ph, pw, what=str((cin, cout, kh, kw, h, w_)))
+
+
+@pytest.mark.parametrize("variant", [1, 3])
+def test_conv2d_variants_agree_with_oracle(B, variant):
+    """The direct-evaluation kernel (1) and the 4-wavefront scalar-read matrix kernel (3)."""
+    r = _rng(variant)
+    x = r.standard_normal((2, 32, 24, 24), dtype=np.float32)
+    w = (r.standard_normal((64, 32, 3, 3), dtype=np.float32) * 0.06).astype(np.float32)
+    B.sws_set_option("conv2d_variant", variant)
+    try:
+        _c2(B, x, w, 1, 1, 1, 1, what="variant %d" % variant)
+    finally:
+        B.sws_set_option("conv2d_variant", 0)
+
+
+def test_conv1d_dense_long_kernel_and_padding(B):
+    """Dense channels with k = 9 (largest single-pass tap count) and padding, ragged length."""
+    r = _rng(99)
+    x = r.standard_normal((3, 16, 2051), dtype=np.float32)
+    w = (r.standard_normal((24, 16, 9), dtype=np.float32) * 0.1).astype(np.float32)
+    _c1(B, x, w, pad=4, what="dense k=9 pad=4")
+    w = (r.standard_normal((24, 16, 11), dtype=np.float32) * 0.1).astype(np.float32)
+    _c1(B, x, w, pad=5, what="dense k=11 pad=5")
+
+
 def test_conv2d_integer_valued_bit_exact(B):
     x = workloads.integer_valued((2, 5, 20, 23), -8, 8, seed=4)
     w = workloads.integer_valued((6, 5, 3, 3), -4, 4, seed=5)

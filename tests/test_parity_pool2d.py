@@ -61,6 +61,25 @@ def test_add_bit_exact_on_integer_valued_input(B):
     assert np.array_equal(y.astype(np.float64), ref)
 
 
+@pytest.mark.parametrize("flags", [2, 4, 6])
+def test_band_kernel_knobs(B, flags):
+    """XCD-contiguous placement and plain stores are measurement knobs, not semantics."""
+    x = np.random.Generator(np.random.PCG64(flags)).standard_normal((3, 5, 60, 112), dtype=np.float32)
+    B.sws_set_option("pool2d_variant", flags)
+    try:
+        _check(B, "max", x, 3, 3, 1, 1, 1, 1)
+        _check(B, "add", x, 3, 3, 2, 2, 1, 1)
+    finally:
+        B.sws_set_option("pool2d_variant", 0)
+
+
+def test_wide_plane_falls_back(B):
+    """A row too wide for a wavefront's LDS slice runs on the direct-evaluation kernel."""
+    x = np.random.Generator(np.random.PCG64(8)).standard_normal((1, 2, 9, 3000), dtype=np.float32)
+    _check(B, "max", x, 3, 3, 1, 1, 1, 1)
+    _check(B, "add", x, 3, 3, 2, 2, 1, 1)
+
+
 def test_tiny_planes(B):
     for shape in [(1, 1, 1, 1), (3, 1, 2, 2), (1, 2, 3, 1), (2, 2, 1, 9)]:
         x = np.random.Generator(np.random.PCG64(11)).standard_normal(shape, dtype=np.float32)

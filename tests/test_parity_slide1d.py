@@ -76,6 +76,24 @@ def test_every_kernel_variant(B, variant, w):
         B.sws_set_option("slide_variant", 0)
 
 
+@pytest.mark.parametrize("bits", [1, 2, 4, 8, 1 | 8, 2 | 4])
+@pytest.mark.parametrize("group", [0, 4, 12, 64])
+def test_scan_kernel_tiling_knobs(B, bits, group):
+    """Unaligned / aligned tiles, plain / non-temporal stores, both workgroup placements and
+    several tiles-per-workgroup counts must all give the same answer."""
+    rng = np.random.Generator(np.random.PCG64(bits * 10 + group))
+    x = rng.standard_normal((9, 4099), dtype=np.float32)
+    B.sws_set_option("slide_chunk", bits)
+    B.sws_set_option("slide_group", group)
+    try:
+        for w in (2, 17, 100, 255, 700):
+            _check(B, "add", x, w, scale=0.5, what="bits %d group %d w %d" % (bits, group, w))
+            _check(B, "max", x, w, what="bits %d group %d w %d" % (bits, group, w))
+    finally:
+        B.sws_set_option("slide_chunk", 0)
+        B.sws_set_option("slide_group", 0)
+
+
 def test_many_short_rows(B):
     """More rows than any grid dimension trick would hide: 40000 rows of 37."""
     rng = np.random.Generator(np.random.PCG64(77))
