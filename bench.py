@@ -166,6 +166,20 @@ def run_only(torch, B, workloads, name, steps):
             w = int(wn[1:])
             y = torch.empty(256, 128, LEN5 - w + 1, device="cuda")
             fn = lambda: B.sws_slide1d(0 if opn == "add" else 1, x, w, 1.0 / w, y=y)
+    elif name.startswith("cfg1_"):
+        x1, t1 = workloads.make(1)
+        x1, t1 = g(x1), g(t1)
+        y = torch.empty(1, 1, 1048572, device="cuda")
+        if name == "cfg1_corr_k5":
+            fn = lambda: B.sws_conv1d(x1, t1, y=y)
+        else:
+            op = 1 if "max" in name else 0
+            fn = lambda: B.sws_slide1d(op, x1, 5, 0.2, y=y)
+    elif name in ("cfg2_avgpool_w3", "cfg2_maxpool_w3"):
+        x2 = g(workloads.make(2)[0])
+        y = torch.empty(16, 64, 4094, device="cuda")
+        op = 1 if "max" in name else 0
+        fn = lambda: B.sws_slide1d(op, x2, 3, 1 / 3, y=y)
     elif name.startswith("cfg3_"):
         x3 = g(workloads.make(3)[0])
         s = int(name[-1])

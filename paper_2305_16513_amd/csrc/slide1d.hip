@@ -192,14 +192,19 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
     int64_t gt = unit * group + wave;
     int64_t gt_end = (unit + 1) * group;
     if (gt_end > n_tiles) gt_end = n_tiles;
-    int64_t r = gt / tiles_per_row;
+    // row and tile-in-row of my first tile; the float reciprocal is exact below 2^22 tiles
+    int64_t r;
+    if (n_tiles < (1LL << 22)) r = (int)(((float)(int)gt + 0.5f) * (1.0f / (float)tiles_per_row));
+    else if (n_tiles < 4294967296LL) r = (uint32_t)gt / (uint32_t)tiles_per_row;
+    else r = gt / tiles_per_row;
     int t = (int)(gt - r * tiles_per_row);
     const bool aligned = (flags & 4) != 0;          // tile origins on 64-byte boundaries of y
 
     // Lane constants.  This lane scans local positions C*lane .. C*lane+C-1; m[k] is the reset
     // mask of element k: a segment (S elements, counted from the tile origin) starts there.
     // m[C] belongs to the first element of the next lane.
-    const int q0 = (C * lane) - S * (int)(((float)(C * lane) + 0.5f) * (1.0f / (float)S));   // (C*lane) % S
+    const float inv_s = 1.0f / (float)S;
+    const int q0 = (C * lane) - S * (int)(((float)(C * lane) + 0.5f) * inv_s);                // (C*lane) % S
     float m[C + 1];
     if (S > C) {
         // at most one segment start inside k = 0 .. C: at kb = distance to the next multiple of S
@@ -215,7 +220,10 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
         }
     }
     const int n_pre = (q0 + C - 1) / C;             // earlier lanes holding part of my first segment
-    const int rem = (S - (q0 + C) % S) % S;         // elements of my last segment beyond my chunk
+    int qe = q0 + C;                                // (q0 + C) % S: offset of the next lane's first element
+    if (S > C) qe = qe >= S ? qe - S : qe;
+    else qe -= S * (int)(((float)qe + 0.5f) * inv_s);
+    const int rem = qe == 0 ? 0 : S - qe;           // elements of my last segment beyond my chunk
     const int n_suf = (rem + C - 1) / C;            // later lanes holding them
     const int max_reach = (S - 1 + C - 1) / C;
     const int sh = S & 3;                           // misalignment of Pre[q+S] against strips
@@ -229,18 +237,20 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
 
     for (; gt < gt_end; gt += kWavesPerWg) {
         const float *xr = x + r * (int64_t)len;
-        float *yr = y + r * (int64_t)lo;
         // With aligned tiles the origin is pulled back so that (r*lo + t0) is a multiple of 16
         // floats: every 1 KB strip store then starts on a 64-byte line.  The first tile of a row
         // may start before the row (t0 < 0); those outputs are not stored.
         const int t0 = t * tout - (aligned ? (int)((r * lo) & 15) : 0);
         const int qlo = t0 < 0 ? -t0 : 0;
+        // tile-relative bases: uniform 64-bit arithmetic once, 32-bit lane offsets afterwards
+        const float *xt = xr + t0;
+        float *yt = y + r * (int64_t)lo + t0;
         // ---- stage the tile: coalesced strips -> LDS, identity outside the row
         if (t0 >= 0 && t0 <= len - N) {
 #pragma unroll
             for (int j = 0; j < NS; ++j) {
                 const int q = j * 256 + 4 * lane;
-                *(v4f *)(A + strip_pos + 256 * j) = *(const v4f_u *)(xr + t0 + q);
+                *(v4f *)(A + strip_pos + 256 * j) = *(const v4f_u *)(xt + q);
             }
         } else {
 #pragma unroll
@@ -318,13 +328,13 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
             o.x = O::f(s4v.x, pn.x); o.y = O::f(s4v.y, pn.y); o.z = O::f(s4v.z, pn.z); o.w = O::f(s4v.w, pn.w);
             if (OP == SWS_OP_ADD) o *= scale;
             if (q >= qlo && q + 4 <= lim) {
-                if (flags & 2) __builtin_nontemporal_store(o, (v4f_u *)(yr + t0 + q));
-                else *(v4f_u *)(yr + t0 + q) = o;
+                if (flags & 2) __builtin_nontemporal_store(o, (v4f_u *)(yt + q));
+                else *(v4f_u *)(yt + q) = o;
             } else {
-                if (q + 0 >= qlo && q + 0 < lim) yr[t0 + q + 0] = o.x;
-                if (q + 1 >= qlo && q + 1 < lim) yr[t0 + q + 1] = o.y;
-                if (q + 2 >= qlo && q + 2 < lim) yr[t0 + q + 2] = o.z;
-                if (q + 3 >= qlo && q + 3 < lim) yr[t0 + q + 3] = o.w;
+                if (q + 0 >= qlo && q + 0 < lim) yt[q + 0] = o.x;
+                if (q + 1 >= qlo && q + 1 < lim) yt[q + 1] = o.y;
+                if (q + 2 >= qlo && q + 2 < lim) yt[q + 2] = o.z;
+                if (q + 3 >= qlo && q + 3 < lim) yt[q + 3] = o.w;
             }
         }
         wave_lds_sync();                                         // the next tile overwrites A
