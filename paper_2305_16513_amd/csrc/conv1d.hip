@@ -27,13 +27,14 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// LDS layout of a wave tile: rows of 64 floats (16 groups of 4); group c of row r is stored at
-// group (c ^ (r & 3)).  Strips (16 consecutive lanes = one row) and per-lane windows (lane l
-// reads groups 4*l + u; 16 lanes span 4 rows whose group sets the XOR makes disjoint) both
-// touch all 64 banks exactly once per 16 lanes of a 128-bit access.
+// LDS layout of a wave tile: group g (4 floats) is stored at
+//     g ^ ((g >> 3) & 3) ^ (((g >> 5) & 1) << 3),
+// which keeps 128-bit accesses conflict-free for strips (consecutive lanes, consecutive groups)
+// and for per-lane windows (consecutive lanes 4 groups apart) on 32- and 64-bank LDS alike.
 __host__ __device__ constexpr int lds_pos(int q)
 {
-    return (q & ~63) | (((((q >> 2) & 15) ^ ((q >> 6) & 3))) << 2) | (q & 3);
+    const int g = q >> 2;                            // group of 4 floats
+    return ((g ^ ((g >> 3) & 3) ^ (((g >> 5) & 1) << 3)) << 2) | (q & 3);
 }
 
 template <int KB4>

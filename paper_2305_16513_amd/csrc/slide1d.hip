@@ -125,14 +125,17 @@ __global__ __launch_bounds__(kThreads) void slide_direct_kernel(const float *__r
 // ------------------------------------------------------------------------------------------
 // Large windows: in-segment prefix + suffix sums, one (+) per output.
 // ------------------------------------------------------------------------------------------
-// LDS layout of one wave tile.  The tile is 16 rows of 64 floats (= 16 groups of 4); group c
-// of row r is stored at group (c ^ (r & 3)) of the same row.  Both access shapes then cover
-// all 64 banks exactly once per 16 lanes of a 128-bit access: strips (16 consecutive lanes
-// read one whole row) and chunks (lane l reads the 4 groups 4*l .. 4*l+3, 16 lanes span 4
-// rows whose group sets the XOR makes disjoint).
+// LDS layout of one wave tile: the tile is 256 groups of 4 floats, and group g is stored at
+//     g ^ ((g >> 3) & 3) ^ (((g >> 5) & 1) << 3).
+// Folding bits 3-4 into bits 0-1 and bit 5 into bit 3 makes both access shapes of a 128-bit
+// LDS instruction conflict-free, whether the hardware serves 8 lanes (32 banks) or 16 lanes
+// (64 banks) per cycle: strips (consecutive lanes read consecutive groups) and chunks (lane l
+// reads groups 4*l .. 4*l+3, i.e. consecutive lanes are 4 groups apart).  The permutation
+// only touches bits 0-3 of g, so it commutes with adding multiples of 64 groups (a strip).
 __device__ __forceinline__ int lds_pos(int q)
 {
-    return (q & ~63) | (((((q >> 2) & 15) ^ ((q >> 6) & 3))) << 2) | (q & 3);
+    const int g = q >> 2;                            // group of 4 floats
+    return ((g ^ ((g >> 3) & 3) ^ (((g >> 5) & 1) << 3)) << 2) | (q & 3);
 }
 
 // In-segment scan step with the reset folded into arithmetic: acc is forgotten where a new
