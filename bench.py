@@ -147,6 +147,53 @@ def ops_table(torch, B, workloads, iters=20):
     return out
 
 
+def sweeps_table(torch, B, workloads, iters=20):
+    """The shapes of the paper's two experiments (Experiments section): 1-D convolution of
+    single-channel sequences over the filter sizes of its first figure, and a 51-tap kernel with
+    dilation 8 at the output sizes of its second figure (one sequence: launch-latency bound;
+    plus a batched depthwise form that fills the device).  GB/s on algorithmic bytes, TFLOP/s on
+    2*k FLOP per output; the vector-ALU peak without packed fp32 is 78.6 TFLOP/s."""
+    g = lambda a: torch.from_numpy(a).cuda()
+    out = {"filter_sweep": {}, "dilated_single": {}, "dilated_batched": {}}
+    c6 = workloads.CONFIGS[6]
+    rows, length = c6.x_shape[0], c6.x_shape[2]
+    x6 = g(workloads.make(6)[0])
+    for k in workloads.FILTER_SIZES:
+        taps = g(workloads.make(6, x_shape=(1,), wgt_shape=(1, 1, k))[1])
+        lo = length - k + 1
+        y = torch.empty(rows, 1, lo, device="cuda")
+        ms = time_launches(torch, lambda: B.sws_conv1d(x6, taps, y=y), iters)
+        nb, fl = 4 * rows * (length + lo) + 4 * k, 2.0 * k * rows * lo
+        out["filter_sweep"]["k%d" % k] = {"ms": round(ms, 4), "GBps": round(nb / ms / 1e6, 1),
+                                          "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                                          "TFLOPs": round(fl / ms / 1e9, 2)}
+        del y
+    del x6
+    torch.cuda.empty_cache()
+    k, d = workloads.DILATED_K, workloads.DILATED_D
+    for q in workloads.DILATED_OUTPUT_SIZES:
+        x7, taps = workloads.make(7, x_shape=(1, 1, q + (k - 1) * d), wgt_shape=(1, 1, k))
+        x7, taps = g(x7), g(taps)
+        y = torch.empty(1, 1, q, device="cuda")
+        ms = time_launches(torch, lambda: B.sws_conv1d(x7, taps, 1, 0, d, 1, y=y), iters)
+        out["dilated_single"]["q%d" % q] = {"us": round(ms * 1e3, 2), "GFLOPs": round(2.0 * k * q / ms / 1e6, 1)}
+    c7 = workloads.CONFIGS[7]
+    ch, length = c7.x_shape[1], c7.x_shape[2]
+    x7, taps = workloads.make(7)
+    x7, taps = g(x7), g(taps)
+    lo = length - (k - 1) * d
+    y = torch.empty(1, ch, lo, device="cuda")
+    ms = time_launches(torch, lambda: B.sws_conv1d(x7, taps, 1, 0, d, ch, y=y), iters)
+    nb, fl = 4 * ch * (length + lo) + 4 * ch * k, 2.0 * k * ch * lo
+    out["dilated_batched"]["dwconv_k51_d8"] = {"ms": round(ms, 4), "GBps": round(nb / ms / 1e6, 1),
+                                               "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                                               "TFLOPs": round(fl / ms / 1e9, 2),
+                                               "frac_valu_peak": round(fl / ms / 1e9 / 78.6, 4)}
+    del x7, y
+    torch.cuda.empty_cache()
+    return out
+
+
 def run_only(torch, B, workloads, name, steps):
     """Launch one operator `steps` times (for rocprofv3 runs that should see a single kernel)."""
     g = lambda a: torch.from_numpy(a).cuda()
@@ -197,6 +244,18 @@ def run_only(torch, B, workloads, name, steps):
         x2, w2 = g(x2), g(w2)
         y = torch.empty(16, 64, 4094, device="cuda")
         fn = lambda: B.sws_conv1d(x2, w2, y=y)
+    elif name == "exp_dwconv_k51_d8":
+        x7, taps = workloads.make(7)
+        x7, taps = g(x7), g(taps)
+        k, d = workloads.DILATED_K, workloads.DILATED_D
+        y = torch.empty(1, x7.shape[1], x7.shape[2] - (k - 1) * d, device="cuda")
+        fn = lambda: B.sws_conv1d(x7, taps, 1, 0, d, x7.shape[1], y=y)
+    elif name.startswith("exp_conv1d_k"):
+        k = int(name[len("exp_conv1d_k"):])
+        x6 = g(workloads.make(6)[0])
+        taps = g(workloads.make(6, x_shape=(1,), wgt_shape=(1, 1, k))[1])
+        y = torch.empty(x6.shape[0], 1, x6.shape[2] - k + 1, device="cuda")
+        fn = lambda: B.sws_conv1d(x6, taps, y=y)
     else:
         raise SystemExit("bench.py --only: unknown operator %r" % name)
     for _ in range(steps):
@@ -334,6 +393,7 @@ def main():
     torch.cuda.empty_cache()
     if not args.no_ops:
         result["ops"] = ops_table(torch, B, workloads)
+        result["experiments"] = sweeps_table(torch, B, workloads)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(x_host, taps_host)
     print(json.dumps(result))

@@ -10,6 +10,11 @@
 //    the k taps (held in scalar registers) over it, producing 16 consecutive outputs.
 //    Global traffic is coalesced 128-bit strips; LDS turns strips into per-lane windows
 //    and the per-lane outputs back into strips.
+//
+//  * conv1d_thin_dilated_kernel: the same with taps spaced d > 1 apart.  A dilated
+//    correlation is d independent undilated ones on the phase subsequences x[p + d*m], so the
+//    tile is staged phase-major in LDS and a lane slides the taps over a register window of
+//    one phase, exactly as above; outputs return through LDS to coalesced strips.
 #include "sws_internal.h"
 
 namespace sws {
@@ -167,6 +172,189 @@ hipError_t launch_thin(const float *x, const float *wgt, float *y, int64_t rows_
     return hipGetLastError();
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Dilated thin convolution.  A wave tile is TO = 16*d*G consecutive outputs (G = 64 / d lanes per
+// phase); lane (p, g) produces the 16 outputs p + d*(16g + e), e < 16, which need phase p of the
+// input at indices 16g .. 16g + 15 + k - 1.  LDS holds the tile phase-major: input q of the tile
+// (phase q % d, index m = q / d) lives at  (q % d) * MP + m + 4*(m >> 4)  — 4 floats of padding
+// per 16 keep the 128-bit window reads of neighbouring lanes on different banks.
+constexpr int kDilSliceMax = 3072;                   // floats of LDS per wavefront
+constexpr int kDilMaxD = 64;
+
+__device__ __forceinline__ int dil_out_pos(int q)    // outputs on their way back to strips
+{
+    const int g = q >> 2;
+    return ((g ^ ((g >> 3) & 7) ^ (g >> 6)) << 2) | (q & 3);
+}
+
+struct DilPlan {
+    int d, G, MP, slice, TO, NI;
+    float inv_d;
+};
+
+template <int KB4>
+__global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
+    const float *__restrict__ x, const float *__restrict__ wgt, float *__restrict__ y, int L, int Lo, int k,
+    int pad, DilPlan pl, int Cin, int Cout, int cog, int tiles_per_row, int group, int chunks_per_row,
+    int64_t n_units)
+{
+    constexpr int K4 = 4 * KB4;
+    constexpr int NG = KB4 + 4;
+    extern __shared__ __attribute__((aligned(16))) float lds_dyn[];
+
+    const int64_t unit = xcd_unit(n_units);
+    if (unit < 0) return;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    float *A = lds_dyn + wave * pl.slice;
+    const int64_t ro = unit / chunks_per_row;
+    const int chunk = (int)(unit - ro * chunks_per_row);
+    const int64_t b = ro / Cout;
+    const int co = (int)(ro - b * Cout);
+    const float *xr = x + (b * Cin + co / cog) * (int64_t)L;
+    const float *wr = wgt + (int64_t)co * k;
+    float *yr = y + ro * (int64_t)Lo;
+    const int c = (int)((ro * Lo) & 15);             // 64-byte-aligned strip stores, as in the undilated kernel
+    const int d = pl.d, MP = pl.MP, TO = pl.TO, NI = pl.NI;
+
+    float f[K4];
+#pragma unroll
+    for (int t = 0; t < K4; ++t) f[t] = (t < k) ? wr[t] : 0.0f;
+
+    const int ph = lane / pl.G, gl = lane - ph * pl.G;
+    const bool active = lane < d * pl.G;
+    const int wbase = active ? ph * MP + 20 * gl : 0;
+    const int n_strips = (NI + 255) >> 8;
+
+    int t_end = (chunk + 1) * group;
+    if (t_end > tiles_per_row) t_end = tiles_per_row;
+    for (int t = chunk * group + wave; t < t_end; t += kWavesPerWg) {
+        const int t0 = t * TO - c;
+        const int p0 = t0 - pad;                     // global index of tile input 0
+        // ---- stage: coalesced strips -> phase-major LDS, four strips in flight at a time
+        for (int j0 = 0; j0 < n_strips; j0 += 4) {
+            v4f g4[4];
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const int pg = p0 + (j0 + jj) * 256 + 4 * lane;
+                int pc = pg < 0 ? 0 : pg;
+                pc = pc > L - 4 ? L - 4 : pc;        // always a legal address (L >= 4)
+                g4[jj] = *(const v4f_u *)(xr + pc);
+            }
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const int q = (j0 + jj) * 256 + 4 * lane;
+                const int pg = p0 + q;
+                float e[4] = {g4[jj].x, g4[jj].y, g4[jj].z, g4[jj].w};
+                if (pg < 0 || pg > L - 4) {          // row border: pick the wanted elements, zero outside
+                    int pc = pg < 0 ? 0 : pg;
+                    pc = pc > L - 4 ? L - 4 : pc;
+                    const int sft = pg - pc;
+                    float r[4];
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc) {
+                        const int want = cc + sft;   // index into the loaded group
+                        float v = 0.0f;
+                        v = want == 0 ? e[0] : v;
+                        v = want == 1 ? e[1] : v;
+                        v = want == 2 ? e[2] : v;
+                        v = want == 3 ? e[3] : v;
+                        r[cc] = (pg + cc >= 0 && pg + cc < L) ? v : 0.0f;
+                    }
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc) e[cc] = r[cc];
+                }
+                int m = (int)(((float)q + 0.5f) * pl.inv_d);   // q / d, exact for q < 2^20
+                int p = q - m * d;
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) {
+                    if (q + cc < NI) A[p * MP + m + 4 * (m >> 4)] = e[cc];
+                    if (++p == d) { p = 0; ++m; }
+                }
+            }
+        }
+        wave_lds_sync();
+        // ---- my window: phase ph, indices 16*gl .. 16*gl + K4 + 15
+        float xw[K4 + 16];
+#pragma unroll
+        for (int u = 0; u < NG; ++u) {
+            const v4f g = *(const v4f *)(A + wbase + 4 * u + 4 * (u >> 2));
+            xw[4 * u] = g.x; xw[4 * u + 1] = g.y; xw[4 * u + 2] = g.z; xw[4 * u + 3] = g.w;
+        }
+        float acc[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
+#pragma unroll
+        for (int tt = 0; tt < K4; ++tt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[e] = fmaf(f[tt], xw[e + tt], acc[e]);
+        wave_lds_sync();
+        // ---- outputs p + d*(16 gl + e) -> LDS -> strips
+        if (active) {
+            int q = ph + d * 16 * gl;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) { A[dil_out_pos(q)] = acc[e]; q += d; }
+        }
+        wave_lds_sync();
+        int lim = Lo - t0;
+        if (lim > TO) lim = TO;
+        const int qlo = t0 < 0 ? -t0 : 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int q = j * 256 + 4 * lane;
+            if (q >= lim) continue;
+            const v4f o = *(const v4f *)(A + dil_out_pos(q));
+            if (q >= qlo && q + 4 <= lim) {
+                __builtin_nontemporal_store(o, (v4f_u *)(yr + t0 + q));
+            } else {
+                if (q + 0 >= qlo && q + 0 < lim) yr[t0 + q + 0] = o.x;
+                if (q + 1 >= qlo && q + 1 < lim) yr[t0 + q + 1] = o.y;
+                if (q + 2 >= qlo && q + 2 < lim) yr[t0 + q + 2] = o.z;
+                if (q + 3 >= qlo && q + 3 < lim) yr[t0 + q + 3] = o.w;
+            }
+        }
+        wave_lds_sync();
+    }
+}
+
+// Tile geometry of the dilated kernel; false if the tile does not fit a wavefront's LDS slice.
+bool plan_dilated(int d, int K4, DilPlan *pl)
+{
+    if (d < 2 || d > kDilMaxD) return false;
+    pl->d = d;
+    pl->G = 64 / d;
+    const int M = 16 * pl->G + K4;                   // staged indices per phase
+    int MP = M + 4 * ((M + 15) / 16);
+    if (((MP / 4) & 1) == 0) MP += 4;                // odd number of bank quads between phases
+    pl->MP = MP;
+    pl->TO = 16 * d * pl->G;
+    pl->NI = d * M;
+    pl->slice = d * MP > 1024 ? d * MP : 1024;       // the output exchange uses the first 1024 floats
+    pl->inv_d = 1.0f / (float)d;
+    return pl->slice <= kDilSliceMax;
+}
+
+template <int KB4>
+hipError_t launch_thin_dilated(const float *x, const float *wgt, float *y, int64_t rows_out, int L, int Lo, int k,
+                               int pad, const DilPlan &pl, int Cin, int Cout, int cog, hipStream_t s)
+{
+    const int tiles_per_row = (Lo + 15 + pl.TO - 1) / pl.TO;
+    int64_t g = 4 * kWavesPerWg;
+    while (g > kWavesPerWg && rows_out * ((tiles_per_row + g - 1) / g) < 2048) g /= 2;   // small problems: more workgroups
+    if (g_opt.slide_group > 0) g = g_opt.slide_group;
+    if (g > tiles_per_row) g = tiles_per_row;
+    const int group = (int)g;
+    const int chunks_per_row = (tiles_per_row + group - 1) / group;
+    const int64_t n_units = rows_out * chunks_per_row;
+    const int64_t grid = xcd_grid(n_units);
+    if (grid > 2147483647LL) return hipErrorInvalidValue;
+    const size_t lds_bytes = (size_t)kWavesPerWg * pl.slice * sizeof(float);
+    hipLaunchKernelGGL((conv1d_thin_dilated_kernel<KB4>), dim3((unsigned)grid), dim3(kThreads), lds_bytes, s, x, wgt,
+                       y, L, Lo, k, pad, pl, Cin, Cout, cog, tiles_per_row, group, chunks_per_row, n_units);
+    return hipGetLastError();
+}
+
 constexpr int kThinMaxK = 64;
 
 }  // namespace
@@ -178,9 +366,13 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
     int variant = g_opt.conv1d_variant;
     const bool thin_ok = (Cin / groups == 1) && stride == 1 && dilation == 1 && k <= kThinMaxK;
     const bool dense_ok = groups == 1 && Cin >= 2 && stride == 1 && dilation == 1;
+    DilPlan dpl;
+    const bool thin_dil_ok = (Cin / groups == 1) && stride == 1 && dilation > 1 && k <= kThinMaxK && L >= 4 &&
+                             plan_dilated(dilation, 4 * ((k + 3) / 4), &dpl);
     if (variant == 2 && !thin_ok) variant = 0;
+    if (variant == 4 && !thin_dil_ok) variant = 0;
     if (variant == 3 && !dense_ok) variant = 0;
-    if (variant == 0) variant = thin_ok ? 2 : (dense_ok ? 3 : 1);
+    if (variant == 0) variant = thin_ok ? 2 : (thin_dil_ok ? 4 : (dense_ok ? 3 : 1));
     if (variant == 3) {
         // the dense contraction is the 2-D kernel on images of height 1
         bool taken = false;
@@ -200,6 +392,19 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
         default: break;
         }
 #undef SWS_THIN
+    }
+    if (variant == 4) {
+        const int cog = (int)(Cout / groups);
+#define SWS_THIN_DIL(KB)                                                                                        \
+    case KB:                                                                                                    \
+        return launch_thin_dilated<KB>(x, wgt, y, B * Cout, (int)L, (int)Lo, k, pad, dpl, (int)Cin, (int)Cout, cog, s)
+        switch ((k + 3) / 4) {
+            SWS_THIN_DIL(1); SWS_THIN_DIL(2); SWS_THIN_DIL(3); SWS_THIN_DIL(4); SWS_THIN_DIL(5); SWS_THIN_DIL(6);
+            SWS_THIN_DIL(7); SWS_THIN_DIL(8); SWS_THIN_DIL(9); SWS_THIN_DIL(10); SWS_THIN_DIL(11); SWS_THIN_DIL(12);
+            SWS_THIN_DIL(13); SWS_THIN_DIL(14); SWS_THIN_DIL(15); SWS_THIN_DIL(16);
+        default: break;
+        }
+#undef SWS_THIN_DIL
     }
     return launch_conv1d_naive(x, wgt, y, B, Cin, L, Cout, Lo, k, stride, pad, dilation, groups, s);
 }

@@ -3,7 +3,10 @@
 This module holds input generation only — none of the method's arithmetic —
 so that the GPU path and the CPU oracle can both be fed identical bits.  The
 paper measures on no public dataset (an unspecified "large 1-D input" and a
-scenario from a cited work); these five configurations stand in for them.
+scenario from a cited work); these five configurations stand in for them, and
+configurations 6 and 7 give the two experiments of the Experiments section their shapes
+(a filter-size sweep on a large 1-D input; one very long dilated kernel at growing
+output sizes).
 
 All tensors are float32, finite, and never contain -0.0 (so that max/min have
 a unique bit pattern).  Generation is on the host with numpy's PCG64 so the
@@ -13,7 +16,7 @@ from dataclasses import dataclass, field
 
 import numpy as np
 
-SEED_BASE = 2305165130  # + config number 1..5
+SEED_BASE = 2305165130  # + config number 1..7
 
 
 @dataclass(frozen=True)
@@ -39,7 +42,16 @@ CONFIGS = {
     5: Config(5, "cfg5_large_window_1d", (256, 128, 16384), "uniform", (128, 1, 31), (1.0 / 31.0) ** 0.5,
               ("slide_add_w16", "slide_max_w16", "slide_add_w64", "slide_max_w64",
                "slide_add_w255", "slide_max_w255", "dwconv_k31")),
+    # Experiments section, first figure: single-channel sequences, filter sizes FILTER_SIZES.
+    6: Config(6, "exp_filter_sweep_1d", (64, 1, 4194304), "uniform", (1, 1, 51), 0.2, ("conv1d_k*",)),
+    # Experiments section, second figure: a 51-tap kernel with dilation 8; one sequence whose
+    # output size runs over DILATED_OUTPUT_SIZES, and a batched depthwise form that fills the device.
+    7: Config(7, "exp_dilated_1d", (1, 4096, 65536), "uniform", (4096, 1, 51), 0.2, ("dwconv_k51_d8",)),
 }
+
+FILTER_SIZES = (3, 5, 11, 17, 21, 29, 37, 49, 51)
+DILATED_K, DILATED_D = 51, 8
+DILATED_OUTPUT_SIZES = (1000, 5000, 10000, 50000, 100000)
 
 
 def _draw(rng, shape, dist):

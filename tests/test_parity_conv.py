@@ -71,6 +71,46 @@ def test_conv1d_stride_pad_dilation_groups(B, stride, pad, dilation, groups):
     _c1(B, x, w, stride, pad, dilation, groups, what=str((stride, pad, dilation, groups)))
 
 
+@pytest.mark.parametrize("dilation", [2, 3, 4, 5, 8, 16, 33, 64])
+@pytest.mark.parametrize("k", [2, 3, 17, 51])
+def test_conv1d_dilated_single_channel(B, dilation, k):
+    """Taps spaced `dilation` apart on one long sequence (the shape of the dilated-kernel
+    experiment of the Experiments section); several tiles and a ragged tail."""
+    length = (k - 1) * dilation + 2500
+    r = _rng(dilation * 100 + k)
+    x = (r.random((2, 1, length), dtype=np.float32) * 2 - 1).astype(np.float32)
+    w = (r.standard_normal((1, 1, k), dtype=np.float32) / np.sqrt(k)).astype(np.float32)
+    _c1(B, x, w, dilation=dilation, what="dil=%d k=%d" % (dilation, k))
+
+
+@pytest.mark.parametrize("dilation,k,pad", [(2, 5, 4), (8, 51, 200), (7, 9, 3), (64, 4, 100), (16, 33, 256)])
+def test_conv1d_dilated_depthwise_padded(B, dilation, k, pad):
+    r = _rng(dilation * 7 + k)
+    x = r.standard_normal((2, 6, 1500), dtype=np.float32)
+    w = (r.standard_normal((12, 1, k), dtype=np.float32) / np.sqrt(k)).astype(np.float32)   # two outputs per input channel
+    _c1(B, x, w, pad=pad, dilation=dilation, groups=6, what="dw dil=%d k=%d pad=%d" % (dilation, k, pad))
+
+
+def test_conv1d_dilated_short_rows_and_fallbacks(B):
+    r = _rng(99)
+    # rows shorter than one tile, span equal to the row, and a dilation beyond the tuned kernel's range
+    for length, k, dil in [(9, 3, 4), (101, 51, 2), (40, 2, 39), (700, 3, 100), (5000, 64, 64)]:
+        x = r.standard_normal((3, 2, length), dtype=np.float32)
+        w = r.standard_normal((2, 1, k), dtype=np.float32)
+        _c1(B, x, w, dilation=dil, groups=2, what="L=%d k=%d dil=%d" % (length, k, dil))
+
+
+def test_conv1d_dilated_integer_valued_bit_exact_and_variants_agree(B):
+    x = workloads.integer_valued((2, 3, 3000), -8, 8, seed=5)
+    w = workloads.integer_valued((3, 1, 21), -4, 4, seed=6)
+    ref, _ = oracle.conv1d(x, w, 1, 80, 8, 3)
+    for variant in (0, 4, 1):
+        B.sws_set_option("conv1d_variant", variant)
+        y = to_host(B.sws_conv1d(to_gpu(x), to_gpu(w), 1, 80, 8, 3))
+        assert np.array_equal(y.astype(np.float64), ref), "variant %d" % variant
+    B.sws_set_option("conv1d_variant", 0)
+
+
 def test_conv1d_integer_valued_bit_exact(B):
     x = workloads.integer_valued((2, 6, 500), -8, 8, seed=1)
     w = workloads.integer_valued((4, 6, 5), -4, 4, seed=2)
