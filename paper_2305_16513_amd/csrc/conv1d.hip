@@ -32,15 +32,12 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// LDS layout of a wave tile: group g (4 floats) is stored at
-//     g ^ ((g >> 3) & 3) ^ (((g >> 5) & 1) << 3),
-// which keeps 128-bit accesses conflict-free for strips (consecutive lanes, consecutive groups)
-// and for per-lane windows (consecutive lanes 4 groups apart) on 32- and 64-bank LDS alike.
-__host__ __device__ constexpr int lds_pos(int q)
-{
-    const int g = q >> 2;                            // group of 4 floats
-    return ((g ^ ((g >> 3) & 3) ^ (((g >> 5) & 1) << 3)) << 2) | (q & 3);
-}
+// LDS layout of a wave tile: element q lives at q + 4*(q >> 4) — 4 floats of padding after every
+// 16.  A lane's window (16 + k - 1 consecutive elements from 16*lane) then starts 20 floats after
+// its neighbour's, so the 128-bit reads of eight consecutive lanes fall on eight different bank
+// quads, and every access of a lane is one base address plus a compile-time offset.  Strips
+// (lane l at 4*l) see one two-way conflict per eight lanes.
+__host__ __device__ constexpr int lds_pos(int q) { return q + 4 * (q >> 4); }
 
 template <int KB4>
 __global__ __launch_bounds__(kThreads) void conv1d_thin_kernel(
@@ -50,7 +47,7 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_kernel(
     constexpr int K4 = 4 * KB4;                      // taps, zero-padded to a multiple of 4
     constexpr int NI = kTileOut + K4;                // staged inputs per tile
     constexpr int NG = KB4 + 4;                      // 4-float groups in a lane's window
-    constexpr int REGION = (NI + 63) / 64 * 64;
+    constexpr int REGION = (lds_pos(NI) + 63) / 64 * 64;
     __shared__ __attribute__((aligned(16))) float lds[kWavesPerWg * REGION];
 
     const int64_t unit = xcd_unit(n_units);
@@ -69,13 +66,17 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_kernel(
     // 1 KB strip store starts on a 64-byte line of y.  Outputs before the row start are dropped.
     const int c = (int)((ro * Lo) & 15);
 
+    // Taps: one coalesced load (lane t holds tap t, zero beyond k), then broadcast into scalar registers.
     float f[K4];
+    {
+        float tv = wr[lane < k ? lane : 0];
+        tv = lane < k ? tv : 0.0f;
 #pragma unroll
-    for (int t = 0; t < K4; ++t) f[t] = (t < k) ? wr[t] : 0.0f;
+        for (int t = 0; t < K4; ++t) f[t] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(tv), t));
+    }
 
-    int wpos[NG];                                    // LDS offsets of my window's groups
-#pragma unroll
-    for (int u = 0; u < NG; ++u) wpos[u] = lds_pos(16 * lane + 4 * u);
+    const int wbase = 20 * lane;                     // my window: lds_pos(16*lane + 4u) = wbase + 4u + 4*(u >> 2)
+    const int sbase = 4 * lane + 4 * (lane >> 2);    // my strip element: lds_pos(256j + 4*lane) = sbase + 320j
 
     // Strips of one tile (inputs [p0, p0 + NI)): 4 full strips plus the k-1 halo, zero outside the row.
     auto load_tile = [&](int t, v4f (&g)[5]) {
@@ -108,14 +109,14 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_kernel(
         if (t + kWavesPerWg < t_end) load_tile(t + kWavesPerWg, nxt);
         // ---- stage: strips -> LDS
 #pragma unroll
-        for (int j = 0; j < 4; ++j) *(v4f *)(A + lds_pos(j * 256 + 4 * lane)) = cur[j];
-        if (4 * lane < K4) *(v4f *)(A + lds_pos(kTileOut + 4 * lane)) = cur[4];
+        for (int j = 0; j < 4; ++j) *(v4f *)(A + sbase + 320 * j) = cur[j];
+        if (4 * lane < K4) *(v4f *)(A + sbase + 1280) = cur[4];
         wave_lds_sync();
         // ---- my window: inputs 16*lane .. 16*lane + K4 + 15
         float xw[K4 + 16];
 #pragma unroll
         for (int u = 0; u < NG; ++u) {
-            const v4f g = *(const v4f *)(A + wpos[u]);
+            const v4f g = *(const v4f *)(A + wbase + 4 * u + 4 * (u >> 2));
             xw[4 * u] = g.x; xw[4 * u + 1] = g.y; xw[4 * u + 2] = g.z; xw[4 * u + 3] = g.w;
         }
         // ---- slide the taps: acc[e] = sum_t f[t] * x[e + t]
@@ -130,7 +131,7 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_kernel(
         // ---- per-lane outputs -> strips
 #pragma unroll
         for (int u = 0; u < 4; ++u)
-            *(v4f *)(A + wpos[u]) = (v4f){acc[4 * u], acc[4 * u + 1], acc[4 * u + 2], acc[4 * u + 3]};
+            *(v4f *)(A + wbase + 4 * u) = (v4f){acc[4 * u], acc[4 * u + 1], acc[4 * u + 2], acc[4 * u + 3]};
         wave_lds_sync();
         const int lim = Lo - t0;
         const int qlo = t0 < 0 ? -t0 : 0;
@@ -138,7 +139,7 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_kernel(
         for (int j = 0; j < 4; ++j) {
             const int q = j * 256 + 4 * lane;
             if (q >= lim) continue;
-            const v4f o = *(const v4f *)(A + lds_pos(q));
+            const v4f o = *(const v4f *)(A + sbase + 320 * j);
             if (q >= qlo && q + 4 <= lim) {
                 __builtin_nontemporal_store(o, (v4f_u *)(yr + t0 + q));
             } else {
@@ -218,9 +219,14 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
     const int c = (int)((ro * Lo) & 15);             // 64-byte-aligned strip stores, as in the undilated kernel
     const int d = pl.d, MP = pl.MP, TO = pl.TO, NI = pl.NI;
 
+    // Taps: one coalesced load (lane t holds tap t, zero beyond k), then broadcast into scalar registers.
     float f[K4];
+    {
+        float tv = wr[lane < k ? lane : 0];
+        tv = lane < k ? tv : 0.0f;
 #pragma unroll
-    for (int t = 0; t < K4; ++t) f[t] = (t < k) ? wr[t] : 0.0f;
+        for (int t = 0; t < K4; ++t) f[t] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(tv), t));
+    }
 
     const int ph = lane / pl.G, gl = lane - ph * pl.G;
     const bool active = lane < d * pl.G;
