@@ -40,7 +40,7 @@ __device__ __forceinline__ void wave_lds_sync()
 __host__ __device__ constexpr int lds_pos(int q) { return q + 4 * (q >> 4); }
 
 template <int KB4>
-__global__ __launch_bounds__(kThreads) void conv1d_thin_kernel(
+__global__ __launch_bounds__(kThreads, (KB4 <= 8 ? 5 : 4)) void conv1d_thin_kernel(
     const float *__restrict__ x, const float *__restrict__ wgt, float *__restrict__ y, int L, int Lo, int k,
     int pad, int Cin, int Cout, int cog, int tiles_per_row, int group, int chunks_per_row, int64_t n_units)
 {
@@ -160,7 +160,9 @@ hipError_t launch_thin(const float *x, const float *wgt, float *y, int64_t rows_
                        int Cin, int Cout, int cog, hipStream_t s)
 {
     const int tiles_per_row = (Lo + 15 + kTileOut - 1) / kTileOut;     // origins move back by up to 15
-    int64_t g = 4 * kWavesPerWg;                   // taps are loaded once per workgroup: keep a few tiles each
+    // Tiles per workgroup (measured): two per wavefront while HBM is the bound (the tiles in flight
+    // stay a compact window of memory), many once the FMAs dominate (k > 32: fewer prologues).
+    int64_t g = (KB4 <= 8 ? 2 : 16) * kWavesPerWg;
     if (g_opt.slide_group > 0) g = g_opt.slide_group;
     if (g > tiles_per_row) g = tiles_per_row;
     const int group = (int)g;
@@ -179,19 +181,17 @@ hipError_t launch_thin(const float *x, const float *wgt, float *y, int64_t rows_
 // phase); lane (p, g) produces the 16 outputs p + d*(16g + e), e < 16, which need phase p of the
 // input at indices 16g .. 16g + 15 + k - 1.  LDS holds the tile phase-major: input q of the tile
 // (phase q % d, index m = q / d) lives at  (q % d) * MP + m + 4*(m >> 4)  — 4 floats of padding
-// per 16 keep the 128-bit window reads of neighbouring lanes on different banks.
+// per 16 keep the 128-bit window reads of neighbouring lanes on different banks.  Where each
+// element of each staged strip goes does not depend on the tile, so the workgroup computes that
+// table once (in LDS) and every tile's scatter is a table read plus four 32-bit writes.
+// Outputs travel back at q + 4*(q / (16 d)): a lane's 16 outputs are base + d*e, and the lanes of
+// one phase start 16d + 4 floats apart (different banks).
 constexpr int kDilSliceMax = 3072;                   // floats of LDS per wavefront
 constexpr int kDilMaxD = 64;
 
-__device__ __forceinline__ int dil_out_pos(int q)    // outputs on their way back to strips
-{
-    const int g = q >> 2;
-    return ((g ^ ((g >> 3) & 7) ^ (g >> 6)) << 2) | (q & 3);
-}
-
 struct DilPlan {
-    int d, G, MP, slice, TO, NI;
-    float inv_d;
+    int d, G, MP, slice, TO, NI, tab_strips;
+    float inv_d, inv_16d;
 };
 
 template <int KB4>
@@ -208,7 +208,8 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
     if (unit < 0) return;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    float *A = lds_dyn + wave * pl.slice;
+    int4 *tab = (int4 *)lds_dyn;                     // [tab_strips][64]: LDS offsets of a strip's 4 elements
+    float *A = lds_dyn + pl.tab_strips * 256 + wave * pl.slice;
     const int64_t ro = unit / chunks_per_row;
     const int chunk = (int)(unit - ro * chunks_per_row);
     const int64_t b = ro / Cout;
@@ -218,6 +219,24 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
     float *yr = y + ro * (int64_t)Lo;
     const int c = (int)((ro * Lo) & 15);             // 64-byte-aligned strip stores, as in the undilated kernel
     const int d = pl.d, MP = pl.MP, TO = pl.TO, NI = pl.NI;
+
+    // ---- scatter table: element q of the tile -> its phase-major LDS offset; elements the tile does
+    //      not need go to a per-lane dummy slot at the end of the slice
+    {
+        const int dummy = pl.slice - 64 + lane;
+        for (int idx = threadIdx.x; idx < pl.tab_strips * 64; idx += kThreads) {
+            const int q = (idx >> 6) * 256 + 4 * (idx & 63);
+            int m = (int)(((float)q + 0.5f) * pl.inv_d);      // q / d, exact for q < 2^20
+            int p = q - m * d;
+            int a[4];
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) {
+                a[cc] = (q + cc < NI) ? p * MP + m + 4 * (m >> 4) : dummy;
+                if (++p == d) { p = 0; ++m; }
+            }
+            tab[idx] = make_int4(a[0], a[1], a[2], a[3]);
+        }
+    }
 
     // Taps: one coalesced load (lane t holds tap t, zero beyond k), then broadcast into scalar registers.
     float f[K4];
@@ -231,7 +250,14 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
     const int ph = lane / pl.G, gl = lane - ph * pl.G;
     const bool active = lane < d * pl.G;
     const int wbase = active ? ph * MP + 20 * gl : 0;
-    const int n_strips = (NI + 255) >> 8;
+    const int obase = ph + (16 * d + 4) * gl;        // my outputs on their way back: obase + d*e
+    int rpos[4];                                     // my strip groups on their way out
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int q = j * 256 + 4 * lane;
+        rpos[j] = q < TO ? q + 4 * (int)(((float)q + 0.5f) * pl.inv_16d) : 0;
+    }
+    __syncthreads();                                 // table complete
 
     int t_end = (chunk + 1) * group;
     if (t_end > tiles_per_row) t_end = tiles_per_row;
@@ -239,7 +265,7 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
         const int t0 = t * TO - c;
         const int p0 = t0 - pad;                     // global index of tile input 0
         // ---- stage: coalesced strips -> phase-major LDS, four strips in flight at a time
-        for (int j0 = 0; j0 < n_strips; j0 += 4) {
+        for (int j0 = 0; j0 < pl.tab_strips; j0 += 4) {
             v4f g4[4];
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
@@ -250,8 +276,8 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
             }
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
-                const int q = (j0 + jj) * 256 + 4 * lane;
-                const int pg = p0 + q;
+                const int pg = p0 + (j0 + jj) * 256 + 4 * lane;
+                const int4 ad = tab[(j0 + jj) * 64 + lane];
                 float e[4] = {g4[jj].x, g4[jj].y, g4[jj].z, g4[jj].w};
                 if (pg < 0 || pg > L - 4) {          // row border: pick the wanted elements, zero outside
                     int pc = pg < 0 ? 0 : pg;
@@ -271,13 +297,10 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
 #pragma unroll
                     for (int cc = 0; cc < 4; ++cc) e[cc] = r[cc];
                 }
-                int m = (int)(((float)q + 0.5f) * pl.inv_d);   // q / d, exact for q < 2^20
-                int p = q - m * d;
-#pragma unroll
-                for (int cc = 0; cc < 4; ++cc) {
-                    if (q + cc < NI) A[p * MP + m + 4 * (m >> 4)] = e[cc];
-                    if (++p == d) { p = 0; ++m; }
-                }
+                A[ad.x] = e[0];
+                A[ad.y] = e[1];
+                A[ad.z] = e[2];
+                A[ad.w] = e[3];
             }
         }
         wave_lds_sync();
@@ -298,9 +321,9 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
         wave_lds_sync();
         // ---- outputs p + d*(16 gl + e) -> LDS -> strips
         if (active) {
-            int q = ph + d * 16 * gl;
+            int o = obase;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) { A[dil_out_pos(q)] = acc[e]; q += d; }
+            for (int e = 0; e < 16; ++e) { A[o] = acc[e]; o += d; }
         }
         wave_lds_sync();
         int lim = Lo - t0;
@@ -310,7 +333,7 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
         for (int j = 0; j < 4; ++j) {
             const int q = j * 256 + 4 * lane;
             if (q >= lim) continue;
-            const v4f o = *(const v4f *)(A + dil_out_pos(q));
+            const v4f o = *(const v4f *)(A + rpos[j]);
             if (q >= qlo && q + 4 <= lim) {
                 __builtin_nontemporal_store(o, (v4f_u *)(yr + t0 + q));
             } else {
@@ -336,8 +359,11 @@ bool plan_dilated(int d, int K4, DilPlan *pl)
     pl->MP = MP;
     pl->TO = 16 * d * pl->G;
     pl->NI = d * M;
-    pl->slice = d * MP > 1024 ? d * MP : 1024;       // the output exchange uses the first 1024 floats
+    const int out_floats = pl->TO + 4 * pl->G;       // the output exchange reuses the slice
+    pl->slice = (d * MP > out_floats ? d * MP : out_floats) + 64;   // + one dummy slot per lane
+    pl->tab_strips = ((pl->NI + 255) / 256 + 3) & ~3;
     pl->inv_d = 1.0f / (float)d;
+    pl->inv_16d = 1.0f / (float)(16 * d);
     return pl->slice <= kDilSliceMax;
 }
 
@@ -346,7 +372,7 @@ hipError_t launch_thin_dilated(const float *x, const float *wgt, float *y, int64
                                int pad, const DilPlan &pl, int Cin, int Cout, int cog, hipStream_t s)
 {
     const int tiles_per_row = (Lo + 15 + pl.TO - 1) / pl.TO;
-    int64_t g = 4 * kWavesPerWg;
+    int64_t g = (KB4 <= 8 ? 4 : 16) * kWavesPerWg;   // the scatter table is built once per workgroup
     while (g > kWavesPerWg && rows_out * ((tiles_per_row + g - 1) / g) < 2048) g /= 2;   // small problems: more workgroups
     if (g_opt.slide_group > 0) g = g_opt.slide_group;
     if (g > tiles_per_row) g = tiles_per_row;
@@ -355,7 +381,7 @@ hipError_t launch_thin_dilated(const float *x, const float *wgt, float *y, int64
     const int64_t n_units = rows_out * chunks_per_row;
     const int64_t grid = xcd_grid(n_units);
     if (grid > 2147483647LL) return hipErrorInvalidValue;
-    const size_t lds_bytes = (size_t)kWavesPerWg * pl.slice * sizeof(float);
+    const size_t lds_bytes = ((size_t)pl.tab_strips * 256 + (size_t)kWavesPerWg * pl.slice) * sizeof(float);
     hipLaunchKernelGGL((conv1d_thin_dilated_kernel<KB4>), dim3((unsigned)grid), dim3(kThreads), lds_bytes, s, x, wgt,
                        y, L, Lo, k, pad, pl, Cin, Cout, cog, tiles_per_row, group, chunks_per_row, n_units);
     return hipGetLastError();
