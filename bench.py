@@ -62,7 +62,7 @@ def read_traffic(name):
     return None
 
 
-def time_launches(torch, fn, iters, warm=2):
+def time_launches(torch, fn, iters, warm=8):
     """Mean duration in ms of `fn` (one launch) from events on the current stream."""
     for _ in range(warm):
         fn()

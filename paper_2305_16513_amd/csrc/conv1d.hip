@@ -165,8 +165,8 @@ hipError_t launch_thin(const float *x, const float *wgt, float *y, int64_t rows_
     int64_t g = (KB4 <= 8 ? 2 : 16) * kWavesPerWg;
     if (g_opt.slide_group > 0) g = g_opt.slide_group;
     if (g > tiles_per_row) g = tiles_per_row;
-    const int group = (int)g;
-    const int chunks_per_row = (tiles_per_row + group - 1) / group;
+    const int chunks_per_row = (int)((tiles_per_row + g - 1) / g);
+    const int group = (tiles_per_row + chunks_per_row - 1) / chunks_per_row;     // even chunks
     const int64_t n_units = rows_out * chunks_per_row;
     const int64_t grid = xcd_grid(n_units);
     if (grid > 2147483647LL) return hipErrorInvalidValue;
@@ -251,6 +251,7 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
     const bool active = lane < d * pl.G;
     const int wbase = active ? ph * MP + 20 * gl : 0;
     const int obase = ph + (16 * d + 4) * gl;        // my outputs on their way back: obase + d*e
+    const int n_strips = (NI + 255) >> 8;
     int rpos[4];                                     // my strip groups on their way out
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -265,10 +266,11 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
         const int t0 = t * TO - c;
         const int p0 = t0 - pad;                     // global index of tile input 0
         // ---- stage: coalesced strips -> phase-major LDS, four strips in flight at a time
-        for (int j0 = 0; j0 < pl.tab_strips; j0 += 4) {
+        for (int j0 = 0; j0 < n_strips; j0 += 4) {
             v4f g4[4];
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
+                if (j0 + jj >= n_strips) break;      // wave-uniform
                 const int pg = p0 + (j0 + jj) * 256 + 4 * lane;
                 int pc = pg < 0 ? 0 : pg;
                 pc = pc > L - 4 ? L - 4 : pc;        // always a legal address (L >= 4)
@@ -276,6 +278,7 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
             }
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
+                if (j0 + jj >= n_strips) break;
                 const int pg = p0 + (j0 + jj) * 256 + 4 * lane;
                 const int4 ad = tab[(j0 + jj) * 64 + lane];
                 float e[4] = {g4[jj].x, g4[jj].y, g4[jj].z, g4[jj].w};
@@ -372,12 +375,12 @@ hipError_t launch_thin_dilated(const float *x, const float *wgt, float *y, int64
                                int pad, const DilPlan &pl, int Cin, int Cout, int cog, hipStream_t s)
 {
     const int tiles_per_row = (Lo + 15 + pl.TO - 1) / pl.TO;
-    int64_t g = (KB4 <= 8 ? 4 : 16) * kWavesPerWg;   // the scatter table is built once per workgroup
+    int64_t g = (KB4 <= 8 ? 4 : 8) * kWavesPerWg;    // the scatter table is built once per workgroup
     while (g > kWavesPerWg && rows_out * ((tiles_per_row + g - 1) / g) < 2048) g /= 2;   // small problems: more workgroups
     if (g_opt.slide_group > 0) g = g_opt.slide_group;
     if (g > tiles_per_row) g = tiles_per_row;
-    const int group = (int)g;
-    const int chunks_per_row = (tiles_per_row + group - 1) / group;
+    const int chunks_per_row = (int)((tiles_per_row + g - 1) / g);
+    const int group = (tiles_per_row + chunks_per_row - 1) / chunks_per_row;     // even chunks
     const int64_t n_units = rows_out * chunks_per_row;
     const int64_t grid = xcd_grid(n_units);
     if (grid > 2147483647LL) return hipErrorInvalidValue;
