@@ -259,14 +259,14 @@ struct SegPlan {
     unsigned char ci[64], rr[64], ch[64];
 };
 
-template <int KTT>
-__global__ __launch_bounds__(512, 2) void conv2d_mfma_c8_kernel(const float *__restrict__ x,
-                                                                const float *__restrict__ wgt,
-                                                                float *__restrict__ y, ConvGeom g,
-                                                                SegPlan sp)
+template <int KTT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64, 2) void conv2d_mfma_c8_kernel(const float *__restrict__ x,
+                                                                       const float *__restrict__ wgt,
+                                                                       float *__restrict__ y, ConvGeom g,
+                                                                       SegPlan sp)
 {
-    constexpr int WAVES = 8, CIB = 8, XP = 12;
-    constexpr int XS = 8;                             // staged-input registers per lane (<= 64 segments)
+    constexpr int CIB = 8, XP = 12;
+    constexpr int XS = (64 + WAVES - 1) / WAVES;      // staged-input registers per lane (<= 64 segments)
     constexpr int KTMAX = KTT > 0 ? KTT : 9;          // staged-weight registers per lane
     extern __shared__ __attribute__((aligned(16))) float lds[];
     float *Xl = lds;
@@ -325,7 +325,8 @@ __global__ __launch_bounds__(512, 2) void conv2d_mfma_c8_kernel(const float *__r
 #pragma unroll
     for (int s = 0; s < XS; ++s) {
         const int seg = wave + WAVES * s;
-        const int ci = sp.ci[seg], rr = sp.rr[seg], ch = sp.ch[seg];
+        const int sq = seg < 64 ? seg : 63;
+        const int ci = sp.ci[sq], rr = sp.rr[sq], ch = sp.ch[sq];
         const int gh = row0 + rr, cc = ch * 64 + lane, gw = col0 + cc;
         const bool act = seg < nseg && cc < g.Wt;
         xl[s] = act ? (rr * g.Wt + cc) * XP + ci : -1;
@@ -334,8 +335,9 @@ __global__ __launch_bounds__(512, 2) void conv2d_mfma_c8_kernel(const float *__r
     // ---- weight staging plan: thread (co = tid / 8, ci = tid % 8) moves the KT taps of one
     // (output channel, input channel) pair: KT contiguous floats in memory, and in LDS the
     // same word of KT consecutive tap planes (a constant stride).
-    const int w_co = threadIdx.x >> 3, w_ci = threadIdx.x & 7;
-    const bool w_ok = co0 + w_co < g.Cout;
+    const int w_co = (threadIdx.x >> 3) & (kCoTile - 1), w_ci = threadIdx.x & 7;
+    const bool w_mine = threadIdx.x < kCoTile * 8;    // the first 512 threads move the weights
+    const bool w_ok = w_mine && co0 + w_co < g.Cout;
     const float *wsrc = wgt + (w_ok ? ((int64_t)(co0 + w_co) * g.Cin + w_ci) * KT : 0);
     float *wdst = Wl + w_co * XP + w_ci;
 
@@ -357,7 +359,7 @@ __global__ __launch_bounds__(512, 2) void conv2d_mfma_c8_kernel(const float *__r
             if (xl[s] >= 0) Xl[xl[s]] = xg[s] >= 0 ? xreg[s] : 0.0f;
 #pragma unroll
         for (int t = 0; t < KTMAX; ++t)
-            if (t < KT) wdst[t * kCoTile * XP] = w_ok ? wreg[t] : 0.0f;
+            if (t < KT && w_mine) wdst[t * kCoTile * XP] = w_ok ? wreg[t] : 0.0f;
     };
 
     prefetch(0);
@@ -407,7 +409,8 @@ bool plan(ConvGeom &g, int NP, int CIB, int xslots_total, int64_t N, int64_t *n_
     if (g.Wo + g.kw - 1 <= 192) {                     // mode A: flat tiles, full-width rows
         g.mode_b = 0;
         g.Wt = g.Wo + g.kw - 1;
-        const int rows = (g.NP + g.Wo - 2) / g.Wo + 1;                 // output rows a tile can touch
+        // output rows a tile can touch (tiles of whole rows always start on a row)
+        const int rows = (g.NP % g.Wo == 0) ? g.NP / g.Wo : (g.NP + g.Wo - 2) / g.Wo + 1;
         g.NRows = (rows < g.Ho ? rows : g.Ho) + g.kh - 1;
         g.tiles_c = 1;
         g.tiles_per_img = (g.Ho * g.Wo + g.NP - 1) / g.NP;
@@ -460,12 +463,25 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
     int64_t units = 0;
     size_t lds = 0;
     // preferred: channel-fastest tiles with 128-bit operand reads (kh*kw <= 9, Cin % 8 == 0)
-    if (KT <= 9 && Cin % 8 == 0 && g_opt.conv2d_variant != 3 && g_opt.conv2d_variant != 4 &&
-        plan(g, 128, 16, 1 << 30, N, &units, &lds)) {
-        const int nseg = 8 * g.NRows * g.CH;
-        const int xfloats = (g.NRows * g.Wt * 12 + 3) / 4 * 4;
-        const size_t lds8 = 4 * ((size_t)xfloats + (size_t)KT * kCoTile * 12);
-        if (nseg <= 64 && g.NRows < 256 && lds8 <= 64 * 1024 && N <= 65535 && g.co_blocks <= 65535) {
+    if (KT <= 9 && Cin % 8 == 0 && g_opt.conv2d_variant != 3 && g_opt.conv2d_variant != 4) {
+        // Tile width: 8 to 14 wavefronts (128 to 224 positions).  Two workgroups share a compute unit,
+        // so the launch takes ceil(workgroups / 512) rounds of `waves` accumulator blocks each.
+        int best_w = 0;
+        int64_t best_cost = 0;
+        for (int wv = 8; wv <= 14; wv += 2) {
+            if (g_opt.conv2d_variant >= 8 && g_opt.conv2d_variant != wv) continue;     // A/B: force a width
+            ConvGeom t = g;
+            if (!plan(t, 16 * wv, 16, 1 << 30, N, &units, &lds)) continue;
+            const int xfl = (t.NRows * t.Wt * 12 + 3) / 4 * 4;
+            if (8 * t.NRows * t.CH > 64 || t.NRows >= 256 || 4 * ((size_t)xfl + (size_t)KT * kCoTile * 12) > 64 * 1024)
+                continue;
+            const int64_t cost = ((units + 511) / 512) * wv;
+            if (best_w == 0 || cost < best_cost) { best_w = wv; best_cost = cost; }
+        }
+        if (best_w != 0 && N <= 65535 && (Cout + kCoTile - 1) / kCoTile <= 65535) {
+            plan(g, 16 * best_w, 16, 1 << 30, N, &units, &lds);
+            const int xfloats = (g.NRows * g.Wt * 12 + 3) / 4 * 4;
+            const size_t lds8 = 4 * ((size_t)xfloats + (size_t)KT * kCoTile * 12);
             g.CP = xfloats;
             SegPlan sp;
             for (int i = 0; i < 64; ++i) {
@@ -476,12 +492,24 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
             }
             const dim3 grid((unsigned)g.tiles_per_img, (unsigned)g.co_blocks, (unsigned)N);
             *taken = true;
-            if (KT == 9 && kw == 3)
-                hipLaunchKernelGGL((conv2d_mfma_c8_kernel<9>), grid, dim3(512), lds8, s, x, wgt, y, g, sp);
-            else if (KT == 3 && kw == 3)
-                hipLaunchKernelGGL((conv2d_mfma_c8_kernel<3>), grid, dim3(512), lds8, s, x, wgt, y, g, sp);
-            else
-                hipLaunchKernelGGL((conv2d_mfma_c8_kernel<0>), grid, dim3(512), lds8, s, x, wgt, y, g, sp);
+#define SWS_C8(KTT, WV)                                                                                         \
+    hipLaunchKernelGGL((conv2d_mfma_c8_kernel<KTT, WV>), grid, dim3(WV * 64), lds8, s, x, wgt, y, g, sp)
+#define SWS_C8_W(KTT)                                                                                           \
+    switch (best_w) {                                                                                           \
+    case 8: SWS_C8(KTT, 8); break;                                                                              \
+    case 10: SWS_C8(KTT, 10); break;                                                                            \
+    case 12: SWS_C8(KTT, 12); break;                                                                            \
+    default: SWS_C8(KTT, 14); break;                                                                            \
+    }
+            if (KT == 9 && kw == 3) {
+                SWS_C8_W(9)
+            } else if (KT == 3 && kw == 3) {
+                SWS_C8_W(3)
+            } else {
+                SWS_C8_W(0)
+            }
+#undef SWS_C8_W
+#undef SWS_C8
             return hipGetLastError();
         }
     }
