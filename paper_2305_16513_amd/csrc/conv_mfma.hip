@@ -253,10 +253,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void conv2d_mfma_kernel(const float 
 // With the 12-float pitch sixteen consecutive lanes of a 128-bit read hit sixteen distinct
 // bank quads.
 // Staging plan of the input tile, computed on the host and passed by value: segment i (one
-// staged row of one channel, 64 columns wide) is channel seg_ci[i], row seg_rr[i], chunk
-// seg_ch[i].  Wavefront w moves segments w, w+8, ...; the lookups are scalar loads.
+// staged row of one channel, 64 columns wide) packs its channel, row and chunk into e[i].  Wavefront w moves segments w, w+8, ...; the lookups are scalar loads.
 struct SegPlan {
-    unsigned char ci[64], rr[64], ch[64];
+    unsigned int e[64];                               // channel | row << 8 | chunk << 16
 };
 
 template <int KTT, int WAVES>
@@ -326,7 +325,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void conv2d_mfma_c8_kernel(const flo
     for (int s = 0; s < XS; ++s) {
         const int seg = wave + WAVES * s;
         const int sq = seg < 64 ? seg : 63;
-        const int ci = sp.ci[sq], rr = sp.rr[sq], ch = sp.ch[sq];
+        const unsigned int pe = sp.e[sq];             // uniform index: a scalar load
+        const int ci = pe & 255, rr = (pe >> 8) & 255, ch = pe >> 16;
         const int gh = row0 + rr, cc = ch * 64 + lane, gw = col0 + cc;
         const bool act = seg < nseg && cc < g.Wt;
         xl[s] = act ? (rr * g.Wt + cc) * XP + ci : -1;
@@ -486,9 +486,7 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
             SegPlan sp;
             for (int i = 0; i < 64; ++i) {
                 const int ci = i / (g.NRows * g.CH), r2 = i % (g.NRows * g.CH);
-                sp.ci[i] = (unsigned char)(ci < 8 ? ci : 0);
-                sp.rr[i] = (unsigned char)(r2 / g.CH);
-                sp.ch[i] = (unsigned char)(r2 % g.CH);
+                sp.e[i] = (unsigned)(ci < 8 ? ci : 0) | (unsigned)(r2 / g.CH) << 8 | (unsigned)(r2 % g.CH) << 16;
             }
             const dim3 grid((unsigned)g.tiles_per_img, (unsigned)g.co_blocks, (unsigned)N);
             *taken = true;
