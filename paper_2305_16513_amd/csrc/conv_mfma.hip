@@ -258,18 +258,22 @@ struct SegPlan {
     unsigned int e[64];                               // channel | row << 8 | chunk << 16
 };
 
-template <int KTT, int WAVES>
-__global__ __launch_bounds__(WAVES * 64, 2) void conv2d_mfma_c8_kernel(const float *__restrict__ x,
+// (the second launch bound is wavefronts per SIMD: two workgroups per compute unit)
+template <int KTT, int WAVES, int NB>
+__global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c8_kernel(const float *__restrict__ x,
                                                                        const float *__restrict__ wgt,
                                                                        float *__restrict__ y, ConvGeom g,
                                                                        SegPlan sp)
 {
+    // NB blocks of 8 input channels are staged per barrier pair (NB > 1 for few taps, where one
+    // block is too little matrix work between two barriers).
     constexpr int CIB = 8, XP = 12;
-    constexpr int XS = (64 + WAVES - 1) / WAVES;      // staged-input registers per lane (<= 64 segments)
-    constexpr int KTMAX = KTT > 0 ? KTT : 9;          // staged-weight registers per lane
+    constexpr int MAXSEG = NB == 1 ? 64 : 32;         // segments of one channel block (checked by the host)
+    constexpr int XS = (MAXSEG + WAVES - 1) / WAVES;  // staged-input registers per lane and channel block
+    constexpr int KTMAX = KTT > 0 ? KTT : 9;          // staged-weight registers per lane and channel block
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    float *Xl = lds;
-    float *Wl = lds + g.CP;                           // CP = floats reserved for the input tile here
+    float *Xl = lds;                                  // NB input tiles of CP floats
+    float *Wl = lds + NB * g.CP;                      // NB weight blocks of KT * 64 * 12 floats
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -324,7 +328,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void conv2d_mfma_c8_kernel(const flo
 #pragma unroll
     for (int s = 0; s < XS; ++s) {
         const int seg = wave + WAVES * s;
-        const int sq = seg < 64 ? seg : 63;
+        const int sq = seg < MAXSEG ? seg : MAXSEG - 1;
         const unsigned int pe = sp.e[sq];             // uniform index: a scalar load
         const int ci = pe & 255, rr = (pe >> 8) & 255, ch = pe >> 16;
         const int gh = row0 + rr, cc = ch * 64 + lane, gw = col0 + cc;
@@ -341,55 +345,66 @@ __global__ __launch_bounds__(WAVES * 64, 2) void conv2d_mfma_c8_kernel(const flo
     const float *wsrc = wgt + (w_ok ? ((int64_t)(co0 + w_co) * g.Cin + w_ci) * KT : 0);
     float *wdst = Wl + w_co * XP + w_ci;
 
-    float xreg[XS], wreg[KTMAX];
+    float xreg[NB][XS], wreg[NB][KTMAX];
+    const int wblock = KT * kCoTile * XP;             // floats of one weight block in LDS
     // Loads are unconditional (out-of-range slots read valid memory and are dropped when the
     // registers are written to LDS, on the far side of the matrix loop), so nothing forces a
     // wait on a single load.
     auto prefetch = [&](int ci0) {
-        const int xb = ci0 * plane;
 #pragma unroll
-        for (int s = 0; s < XS; ++s) xreg[s] = xn[xg[s] >= 0 ? xb + xg[s] : 0];
-        const float *w = wsrc + (w_ok ? ci0 * KT : 0);
+        for (int nb = 0; nb < NB; ++nb) {
+            const int xb = (ci0 + nb * CIB) * plane;
 #pragma unroll
-        for (int t = 0; t < KTMAX; ++t) wreg[t] = w[t < KT ? t : 0];
+            for (int s = 0; s < XS; ++s) xreg[nb][s] = xn[xg[s] >= 0 ? xb + xg[s] : 0];
+            const float *w = wsrc + (w_ok ? (ci0 + nb * CIB) * KT : 0);
+#pragma unroll
+            for (int t = 0; t < KTMAX; ++t) wreg[nb][t] = w[t < KT ? t : 0];
+        }
     };
     auto commit = [&]() {
 #pragma unroll
-        for (int s = 0; s < XS; ++s)
-            if (xl[s] >= 0) Xl[xl[s]] = xg[s] >= 0 ? xreg[s] : 0.0f;
+        for (int nb = 0; nb < NB; ++nb) {
 #pragma unroll
-        for (int t = 0; t < KTMAX; ++t)
-            if (t < KT && w_mine) wdst[t * kCoTile * XP] = w_ok ? wreg[t] : 0.0f;
+            for (int s = 0; s < XS; ++s)
+                if (xl[s] >= 0) Xl[nb * g.CP + xl[s]] = xg[s] >= 0 ? xreg[nb][s] : 0.0f;
+#pragma unroll
+            for (int t = 0; t < KTMAX; ++t)
+                if (t < KT && w_mine) wdst[nb * wblock + t * kCoTile * XP] = w_ok ? wreg[nb][t] : 0.0f;
+        }
     };
 
     prefetch(0);
-    for (int ci0 = 0; ci0 < g.Cin; ci0 += CIB) {
-        __syncthreads();                              // the previous block has been consumed
+    for (int ci0 = 0; ci0 < g.Cin; ci0 += CIB * NB) {
+        __syncthreads();                              // the previous blocks have been consumed
         commit();
         __syncthreads();
-        if (ci0 + CIB < g.Cin) prefetch(ci0 + CIB);   // in flight during the matrix work below
-        if (KTT > 0) {
+        if (ci0 + CIB * NB < g.Cin) prefetch(ci0 + CIB * NB);   // in flight during the matrix work below
 #pragma unroll
-            for (int tap = 0; tap < (KTT > 0 ? KTT : 1); ++tap) {
-                const int shift = (tap / 3) * g.Wt + (tap % 3);          // KTT > 0 is only used with kw == 3
-                const v4f a4 = *(const v4f *)(Wl + tap * kCoTile * XP + a_lane);
-                const v4f b4 = *(const v4f *)(Xl + shift * XP + b_lane);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, b4.x, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.y, b4.y, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.z, b4.z, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, b4.w, acc, 0, 0, 0);
-            }
-        } else {
-            int ta = 0, tb = 0;
-            for (int tap = 0; tap < KT; ++tap) {
-                const int shift = ta * g.Wt + tb;
-                const v4f a4 = *(const v4f *)(Wl + tap * kCoTile * XP + a_lane);
-                const v4f b4 = *(const v4f *)(Xl + shift * XP + b_lane);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, b4.x, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.y, b4.y, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.z, b4.z, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, b4.w, acc, 0, 0, 0);
-                if (++tb == g.kw) { tb = 0; ++ta; }
+        for (int nb = 0; nb < NB; ++nb) {
+            const float *Xb = Xl + nb * g.CP, *Wb = Wl + nb * wblock;
+            if (KTT > 0) {
+#pragma unroll
+                for (int tap = 0; tap < (KTT > 0 ? KTT : 1); ++tap) {
+                    const int shift = (tap / 3) * g.Wt + (tap % 3);      // KTT > 0 is only used with kw == 3
+                    const v4f a4 = *(const v4f *)(Wb + tap * kCoTile * XP + a_lane);
+                    const v4f b4 = *(const v4f *)(Xb + shift * XP + b_lane);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, b4.x, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.y, b4.y, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.z, b4.z, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, b4.w, acc, 0, 0, 0);
+                }
+            } else {
+                int ta = 0, tb = 0;
+                for (int tap = 0; tap < KT; ++tap) {
+                    const int shift = ta * g.Wt + tb;
+                    const v4f a4 = *(const v4f *)(Wb + tap * kCoTile * XP + a_lane);
+                    const v4f b4 = *(const v4f *)(Xb + shift * XP + b_lane);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, b4.x, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.y, b4.y, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.z, b4.z, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, b4.w, acc, 0, 0, 0);
+                    if (++tb == g.kw) { tb = 0; ++ta; }
+                }
             }
         }
     }
@@ -481,7 +496,11 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
         if (best_w != 0 && N <= 65535 && (Cout + kCoTile - 1) / kCoTile <= 65535) {
             plan(g, 16 * best_w, 16, 1 << 30, N, &units, &lds);
             const int xfloats = (g.NRows * g.Wt * 12 + 3) / 4 * 4;
-            const size_t lds8 = 4 * ((size_t)xfloats + (size_t)KT * kCoTile * 12);
+            const size_t lds1 = 4 * ((size_t)xfloats + (size_t)KT * kCoTile * 12);
+            // few taps: four channel blocks per barrier pair, if they fit
+            const bool nb4 = KT == 3 && kw == 3 && Cin % 32 == 0 && 8 * g.NRows * g.CH <= 32 && 4 * lds1 <= 64 * 1024 &&
+                             g_opt.conv2d_variant != 5;
+            const size_t lds8 = (nb4 ? 4 : 1) * lds1;
             g.CP = xfloats;
             SegPlan sp;
             for (int i = 0; i < 64; ++i) {
@@ -490,21 +509,23 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
             }
             const dim3 grid((unsigned)g.tiles_per_img, (unsigned)g.co_blocks, (unsigned)N);
             *taken = true;
-#define SWS_C8(KTT, WV)                                                                                         \
-    hipLaunchKernelGGL((conv2d_mfma_c8_kernel<KTT, WV>), grid, dim3(WV * 64), lds8, s, x, wgt, y, g, sp)
-#define SWS_C8_W(KTT)                                                                                           \
+#define SWS_C8(KTT, WV, NB)                                                                                     \
+    hipLaunchKernelGGL((conv2d_mfma_c8_kernel<KTT, WV, NB>), grid, dim3(WV * 64), lds8, s, x, wgt, y, g, sp)
+#define SWS_C8_W(KTT, NB)                                                                                       \
     switch (best_w) {                                                                                           \
-    case 8: SWS_C8(KTT, 8); break;                                                                              \
-    case 10: SWS_C8(KTT, 10); break;                                                                            \
-    case 12: SWS_C8(KTT, 12); break;                                                                            \
-    default: SWS_C8(KTT, 14); break;                                                                            \
+    case 8: SWS_C8(KTT, 8, NB); break;                                                                          \
+    case 10: SWS_C8(KTT, 10, NB); break;                                                                        \
+    case 12: SWS_C8(KTT, 12, NB); break;                                                                        \
+    default: SWS_C8(KTT, 14, NB); break;                                                                        \
     }
             if (KT == 9 && kw == 3) {
-                SWS_C8_W(9)
+                SWS_C8_W(9, 1)
+            } else if (nb4) {
+                SWS_C8_W(3, 4)
             } else if (KT == 3 && kw == 3) {
-                SWS_C8_W(3)
+                SWS_C8_W(3, 1)
             } else {
-                SWS_C8_W(0)
+                SWS_C8_W(0, 1)
             }
 #undef SWS_C8_W
 #undef SWS_C8

@@ -53,7 +53,8 @@ def test_conv1d_depthwise(B, k, channels, length):
     _c1(B, x, w, groups=channels, what="dw k=%d C=%d" % (k, channels))
 
 
-@pytest.mark.parametrize("cin,cout,k", [(64, 64, 3), (64, 64, 1), (32, 48, 5), (7, 5, 3), (64, 128, 3), (96, 64, 7)])
+@pytest.mark.parametrize("cin,cout,k", [(64, 64, 3), (64, 64, 1), (32, 48, 5), (7, 5, 3), (64, 128, 3), (96, 64, 7),
+                                         (32, 40, 3), (96, 64, 3), (40, 64, 3), (128, 64, 3)])
 @pytest.mark.parametrize("length", [130, 1027])
 def test_conv1d_dense(B, cin, cout, k, length):
     r = _rng(cin * 31 + cout + k)
@@ -143,6 +144,8 @@ def test_conv2d(B, cin, cout, kh, kw, h, w_, geom):
     (24, 33, 2, 2, 17, 40, 0, 1),      # even tap count, Cout not a multiple of 32
     (64, 64, 6, 6, 20, 20, 2, 2),      # 36 taps
     (64, 64, 7, 7, 20, 20, 3, 3),      # 49 taps: beyond the matrix kernels, direct evaluation
+    (64, 48, 1, 3, 11, 40, 0, 1),      # 1 x 3 taps, Cin % 32 == 0: four channel blocks per barrier pair
+    (32, 64, 1, 3, 3, 500, 0, 1),      # the same on wide rows (column tiles)
 ])
 def test_conv2d_kernel_selection_paths(B, cin, cout, kh, kw, h, w_, ph, pw):
     r = _rng(cin * 7 + cout + kh * 3 + kw)
@@ -151,9 +154,10 @@ def test_conv2d_kernel_selection_paths(B, cin, cout, kh, kw, h, w_, ph, pw):
     _c2(B, x, w, 1, 1, ph, pw, what=str((cin, cout, kh, kw, h, w_)))
 
 
-@pytest.mark.parametrize("variant", [1, 3])
+@pytest.mark.parametrize("variant", [1, 3, 8, 10, 12, 14])
 def test_conv2d_variants_agree_with_oracle(B, variant):
-    """The direct-evaluation kernel (1) and the 4-wavefront scalar-read matrix kernel (3)."""
+    """The direct-evaluation kernel (1), the 4-wavefront scalar-read matrix kernel (3), and the
+    channel-fastest matrix kernel forced to 8 / 10 / 12 / 14 wavefronts per workgroup."""
     r = _rng(variant)
     x = r.standard_normal((2, 32, 24, 24), dtype=np.float32)
     w = (r.standard_normal((64, 32, 3, 3), dtype=np.float32) * 0.06).astype(np.float32)
