@@ -2,7 +2,7 @@
 
 Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
 this package.  It holds the plain definitions (Section 2.2 Eq. 3, Section 2.3,
-Section 2.5 of the paper) written out as loops in C (sws_ref.c) behind a ctypes
+Section 2.4 Eq. 8, Section 2.5 of the paper) written out as loops in C (sws_ref.c) behind a ctypes
 wrapper that does argument marshalling only.  It imports nothing from the GPU
 package and the GPU package imports nothing from here.
 """
@@ -15,5 +15,6 @@ from .ref import (  # noqa: F401
     conv2d,
     pool2d,
     slide1d,
+    slide1d_pair,
     threads,
 )

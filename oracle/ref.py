@@ -43,6 +43,8 @@ def _load():
         lib.sws_ref_pool2d.restype = ctypes.c_int
         lib.sws_ref_pool2d.argtypes = [ctypes.c_int, _fp, _dp, _dp, _i64, _i64, _i64, _i64,
                                        _i32, _i32, _i32, _i32, _i32, _i32, _f64]
+        lib.sws_ref_slide1d_pair.restype = ctypes.c_int
+        lib.sws_ref_slide1d_pair.argtypes = [_fp, _fp, _dp, _dp, _dp, _dp, _i64, _i64, _i32]
         lib.sws_ref_conv1d.restype = ctypes.c_int
         lib.sws_ref_conv1d.argtypes = [_fp, _fp, _dp, _dp, _i64, _i64, _i64, _i64,
                                        _i32, _i32, _i32, _i32, _i32]
@@ -88,6 +90,25 @@ def slide1d(op, x, w, scale=1.0):
     if rc:
         raise ValueError("sws_ref_slide1d rejected its arguments")
     return y, s
+
+
+def slide1d_pair(u, v, w):
+    """u, v: [rows, len] float32 -> (yu, yv, mag_u, mag_v), each [rows, len-w+1] float64:
+    the sliding window sum of the pairs (u_i, v_i) under the operator of Eq. 8."""
+    u, v = _f32(u), _f32(v)
+    if u.ndim == 1:
+        u, v = u[None, :], v[None, :]
+    if u.shape != v.shape:
+        raise ValueError("u and v must have the same shape")
+    rows, length = u.shape
+    lo = length - w + 1
+    if lo < 1:
+        raise ValueError("w must satisfy 1 <= w <= len")
+    out = [np.empty((rows, lo), np.float64) for _ in range(4)]
+    rc = _load().sws_ref_slide1d_pair(_ptr_f(u), _ptr_f(v), *[_ptr_d(a) for a in out], rows, length, w)
+    if rc:
+        raise ValueError("sws_ref_slide1d_pair rejected its arguments")
+    return tuple(out)
 
 
 def pool2d(op, x, kh, kw, sh=1, sw=1, ph=0, pw=0, scale=1.0):

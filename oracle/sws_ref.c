@@ -19,6 +19,9 @@
  *                    checked against an independent formulation.  Taps that
  *                    fall into the padding contribute the identity of the
  *                    operator (they are skipped).
+ *   sws_ref_slide1d_pair  Eq. 3 with the pair operator of Section 2.4, Eq. 8:
+ *                    (u_i, v_i) (+) (u_j, v_j) = (u_i*u_j, u_j*v_i + v_j), i older.
+ *                    Non-commutative; folded strictly left to right.
  *   sws_ref_conv1d   Section 2.5 (convolution = sliding dot product, Eq. 4 per
  *   sws_ref_conv2d   output): cross-correlation (no tap flip), zero padding by
  *                    skipping out-of-range taps, accumulation order ci, kh, kw.
@@ -38,7 +41,10 @@
  * max, the paper's Vector Input algorithm emulated with a non-commutative
  * operator, the dot-product-as-prefix-sum construction of Eq. 7-9, and
  * cross-operator identities (all-ones taps, one-hot taps, rank-1 2-D taps,
- * separability of pooling, strided = subsampled).
+ * separability of pooling, strided = subsampled); for the pair operator a
+ * hand-folded case, u = 1 (sliding add of v), v = 0 (sliding product of u),
+ * exact rational arithmetic on small integers, order sensitivity, and the
+ * Eq. 7 sequence whose full-length window yields the dot product.
  */
 #include <math.h>
 #include <stddef.h>
@@ -212,6 +218,37 @@ int sws_ref_conv2d(const float *x, const float *wgt, double *y, double *abs_sum,
                 y[(u * Ho + ho) * Wo + wo] = acc;
                 if (abs_sum) abs_sum[(u * Ho + ho) * Wo + wo] = mag;
             }
+        }
+    }
+    return 0;
+}
+
+/* Sliding window sum (Eq. 3) of the pairs (u_i, v_i) under the operator of Eq. 8,
+ *   (u_a, v_a) (+) (u_b, v_b) = (u_a*u_b, u_b*v_a + v_b),   a the older (left) operand,
+ * i.e. the composition of the maps z -> u*z + v in index order.  u, v: rows*len floats;
+ * yu, yv: rows*(len-w+1) doubles.  mag_u / mag_v (optional) receive the tolerance scales
+ * |prod u| and sum_j |v_j| * prod_{m>j} |u_m| (the absolute values of the terms of yv). */
+int sws_ref_slide1d_pair(const float *u, const float *v, double *yu, double *yv, double *mag_u, double *mag_v,
+                         int64_t rows, int64_t len, int32_t w)
+{
+    if (rows < 0 || len < 0 || w < 1 || w > len) return 1;
+    if (rows > 0 && (!u || !v || !yu || !yv)) return 1;
+    const int64_t lo = len - w + 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const float *ur = u + r * len, *vr = v + r * len;
+        for (int64_t i = 0; i < lo; ++i) {
+            double U = (double)ur[i], V = (double)vr[i], MV = fabs((double)vr[i]);
+            for (int32_t t = 1; t < w; ++t) {
+                const double uj = (double)ur[i + t], vj = (double)vr[i + t];
+                V = uj * V + vj;                     /* uses the old U nowhere: order of the two lines is free */
+                MV = fabs(uj) * MV + fabs(vj);
+                U = U * uj;
+            }
+            yu[r * lo + i] = U;
+            yv[r * lo + i] = V;
+            if (mag_u) mag_u[r * lo + i] = fabs(U);
+            if (mag_v) mag_v[r * lo + i] = MV;
         }
     }
     return 0;

@@ -468,3 +468,98 @@ def test_abs_sum_is_sum_of_magnitudes():
     _, s = oracle.pool2d(OP_ADD, x2, 3, 3, 1, 1, 1, 1, scale=-0.25)
     y_abs, _ = oracle.pool2d(OP_ADD, np.abs(x2), 3, 3, 1, 1, 1, 1, scale=0.25)
     assert np.allclose(s, y_abs, rtol=1e-14, atol=0)
+
+
+# ----------------------------------------------------------------------------- P9
+# The pair operator of Section 2.4 (Eq. 8) as a sliding window sum (Eq. 3).
+PAIR_GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "pair_hand_cases.txt")
+
+
+def _pair_cases():
+    out = []
+    with open(PAIR_GOLDEN) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            w, us, vs, yus, yvs = [[float(t) for t in p.split()] for p in line.split(";")]
+            out.append((int(w[0]), us, vs, yus, yvs))
+    return out
+
+
+@pytest.mark.parametrize("w,us,vs,yus,yvs", _pair_cases())
+def test_pair_hand_enumerated(w, us, vs, yus, yvs):
+    yu, yv, _, _ = oracle.slide1d_pair(np.array(us, np.float32), np.array(vs, np.float32), w)
+    assert yu[0].tolist() == yus and yv[0].tolist() == yvs
+
+
+@pytest.mark.parametrize("w", [1, 2, 7, 40])
+def test_pair_unit_u_is_sliding_add_and_zero_v_is_sliding_product(w):
+    r = _rng(90 + w)
+    v = r.standard_normal((3, 97), dtype=np.float32)
+    one = np.ones_like(v)
+    yu, yv, mu, mv = oracle.slide1d_pair(one, v, w)
+    add, mag = oracle.slide1d(OP_ADD, v, w)
+    assert np.array_equal(yu, np.ones_like(yu)) and np.allclose(yv, add, rtol=0, atol=1e-13 * mag.max())
+    assert np.allclose(mv, mag, rtol=1e-14)
+    u = (1.0 + 0.25 * r.standard_normal((3, 97))).astype(np.float32)
+    yu, yv, mu, _ = oracle.slide1d_pair(u, np.zeros_like(u), w)
+    prod = np.ones((3, 97 - w + 1))
+    for t in range(w):
+        prod = prod * u[:, t:97 - w + 1 + t].astype(np.float64)
+    assert np.array_equal(yv, np.zeros_like(yv)) and np.allclose(yu, prod, rtol=1e-13) and np.allclose(mu, np.abs(prod), rtol=1e-13)
+    c = np.full((1, 50), 1.5, np.float32)                      # closed form: constant u, constant v
+    yu, yv, _, _ = oracle.slide1d_pair(c, np.full_like(c, 2.0), w)
+    assert np.allclose(yu, 1.5 ** w, rtol=1e-14) and np.allclose(yv, 2.0 * (1.5 ** w - 1) / 0.5, rtol=1e-13)
+
+
+def test_pair_exact_rationals_and_map_composition():
+    """Small integers: the fold equals exact rational arithmetic, and applying the folded map to a
+    point equals applying the w maps z -> u z + v one after the other (oldest first)."""
+    from fractions import Fraction
+    r = _rng(91)
+    u = r.integers(-3, 4, size=(2, 23)).astype(np.float32)
+    v = r.integers(-5, 6, size=(2, 23)).astype(np.float32)
+    for w in (1, 2, 5, 9):
+        yu, yv, _, _ = oracle.slide1d_pair(u, v, w)
+        for row in range(2):
+            for i in range(23 - w + 1):
+                U, V, z = Fraction(1), Fraction(0), Fraction(7, 3)
+                for t in range(w):
+                    uj, vj = Fraction(int(u[row, i + t])), Fraction(int(v[row, i + t]))
+                    U, V = U * uj, uj * V + vj
+                    z = uj * z + vj
+                assert Fraction(yu[row, i]) == U and Fraction(yv[row, i]) == V
+                assert U * Fraction(7, 3) + V == z
+
+
+def test_pair_operator_is_order_sensitive_and_associative():
+    r = _rng(92)
+    u = r.integers(2, 5, size=(1, 12)).astype(np.float32)
+    v = r.integers(1, 9, size=(1, 12)).astype(np.float32)
+    yu, yv, _, _ = oracle.slide1d_pair(u, v, 4)
+    ru, rv, _, _ = oracle.slide1d_pair(u[:, ::-1].copy(), v[:, ::-1].copy(), 4)
+    assert np.array_equal(yu, ru[:, ::-1])                       # products commute ...
+    assert not np.array_equal(yv, rv[:, ::-1])                   # ... the pair operator does not
+    # a window of 4 = (first two) (+) (last two), by associativity
+    au, av, _, _ = oracle.slide1d_pair(u, v, 2)
+    cu = au[:, :-2] * au[:, 2:]
+    cv = au[:, 2:] * av[:, :-2] + av[:, 2:]
+    assert np.array_equal(cu, yu) and np.array_equal(cv, yv)
+
+
+@pytest.mark.parametrize("k", [1, 2, 5, 31])
+def test_pair_full_window_of_gamma_sequence_is_the_dot_product(k):
+    """Eq. 5, 7, 9: the M + 1 pairs built from the masked vectors, folded over one window of
+    length M + 1, carry the dot product in the second component."""
+    r = _rng(93 + k)
+    a = r.integers(-4, 5, size=k).astype(np.float64)
+    a[a == 3] = 0.0                                              # masked entries (Eq. 5)
+    b = r.integers(-6, 7, size=k).astype(np.float64)
+    al = np.where(a == 0, 1.0, a)
+    be = np.where(a == 0, 0.0, b)
+    al = np.where(np.abs(al) == 3, 1.0, al)                      # keep the ratios exactly representable: |alpha| in {1, 2, 4}
+    u = np.array([1.0] + [al[i - 1] / al[i] for i in range(1, k)] + [al[k - 1]], np.float32)
+    v = np.array(list(be) + [0.0], np.float32)
+    _, yv, _, _ = oracle.slide1d_pair(u, v, k + 1)
+    assert yv.shape == (1, 1) and yv[0, 0] == float(np.dot(al, be))
