@@ -154,7 +154,7 @@ def sweeps_table(torch, B, workloads, iters=20):
     plus a batched depthwise form that fills the device).  GB/s on algorithmic bytes, TFLOP/s on
     2*k FLOP per output; the vector-ALU peak without packed fp32 is 78.6 TFLOP/s."""
     g = lambda a: torch.from_numpy(a).cuda()
-    out = {"filter_sweep": {}, "dilated_single": {}, "dilated_batched": {}}
+    out = {"filter_sweep": {}, "dilated_single": {}, "dilated_batched": {}, "pair_operator": {}}
     c6 = workloads.CONFIGS[6]
     rows, length = c6.x_shape[0], c6.x_shape[2]
     x6 = g(workloads.make(6)[0])
@@ -190,6 +190,20 @@ def sweeps_table(torch, B, workloads, iters=20):
                                                "TFLOPs": round(fl / ms / 1e9, 2),
                                                "frac_valu_peak": round(fl / ms / 1e9 / 78.6, 4)}
     del x7, y
+    torch.cuda.empty_cache()
+    # sliding window sum under the pair operator (Section 2.4, Eq. 8): 16 algorithmic bytes per output
+    u, v = workloads.make_pairs()
+    u, v = g(u), g(v)
+    rows, length = u.shape
+    for w in (16, 255):
+        lo = length - w + 1
+        yu, yv = torch.empty(rows, lo, device="cuda"), torch.empty(rows, lo, device="cuda")
+        ms = time_launches(torch, lambda: B.sws_slide1d_pair(u, v, w, yu=yu, yv=yv), iters)
+        nb = 8 * rows * (length + lo)
+        out["pair_operator"]["w%d" % w] = {"ms": round(ms, 4), "GBps": round(nb / ms / 1e6, 1),
+                                           "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+        del yu, yv
+    del u, v
     torch.cuda.empty_cache()
     return out
 
@@ -250,6 +264,13 @@ def run_only(torch, B, workloads, name, steps):
         k, d = workloads.DILATED_K, workloads.DILATED_D
         y = torch.empty(1, x7.shape[1], x7.shape[2] - (k - 1) * d, device="cuda")
         fn = lambda: B.sws_conv1d(x7, taps, 1, 0, d, x7.shape[1], y=y)
+    elif name.startswith("exp_pair_w"):
+        w = int(name[len("exp_pair_w"):])
+        u, v = workloads.make_pairs()
+        u, v = g(u), g(v)
+        yu = torch.empty(u.shape[0], u.shape[1] - w + 1, device="cuda")
+        yv = torch.empty_like(yu)
+        fn = lambda: B.sws_slide1d_pair(u, v, w, yu=yu, yv=yv)
     elif name.startswith("exp_conv1d_k"):
         k = int(name[len("exp_conv1d_k"):])
         x6 = g(workloads.make(6)[0])

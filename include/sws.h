@@ -55,6 +55,20 @@ typedef enum { SWS_OP_ADD = 0, SWS_OP_MAX = 1, SWS_OP_MIN = 2 } sws_op;
 sws_status sws_slide1d(sws_op op, const float *x, float *y, int64_t rows, int64_t len,
                        int32_t w, float scale, void *stream);
 
+/* Sliding window sum (Eq. 3) under the pair operator of Section 2.4, Eq. 8 — the associative,
+ * NON-commutative operator with which the paper writes a dot product as a prefix sum:
+ *
+ *   (u_i, v_i) (+) (u_j, v_j) = (u_i * u_j,  u_j * v_i + v_j),      i older than j
+ *   (yu, yv)[r, i] = (u, v)[r, i] (+) (u, v)[r, i+1] (+) ... (+) (u, v)[r, i+w-1],   0 <= i <= len - w
+ *
+ * i.e. the composition, oldest first, of the w maps z -> u z + v.  Pairs are passed as two
+ * planes.  u = 1 gives the sliding add of v; v = 0 gives the sliding product of u.
+ *   u, v : device, rows*len floats each        yu, yv : device, rows*(len-w+1) floats each
+ * Errors: INVALID_ARG if rows < 0, len < 0, w < 1, w > len, a pointer is NULL while there is
+ * output, or a size overflows int64 / len exceeds 2^31-1. */
+sws_status sws_slide1d_pair(const float *u, const float *v, float *yu, float *yv, int64_t rows,
+                            int64_t len, int32_t w, void *stream);
+
 /* 2-D pooling (Section 2.3 extended to two dimensions) evaluated as separable sliding
  * sums, first along H then along W, on NCHW data:
  *

@@ -19,7 +19,7 @@ _lib = None
 
 _i64, _i32, _f32, _vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
 
-EXPORTS = ("sws_slide1d", "sws_pool2d", "sws_conv1d", "sws_conv2d", "sws_copy", "sws_out_len",
+EXPORTS = ("sws_slide1d", "sws_slide1d_pair", "sws_pool2d", "sws_conv1d", "sws_conv2d", "sws_copy", "sws_out_len",
            "sws_status_string", "sws_set_option", "sws_version")
 
 
@@ -39,6 +39,8 @@ def lib():
         L = ctypes.CDLL(LIB_PATH)
         L.sws_slide1d.restype = ctypes.c_int
         L.sws_slide1d.argtypes = [ctypes.c_int, _vp, _vp, _i64, _i64, _i32, _f32, _vp]
+        L.sws_slide1d_pair.restype = ctypes.c_int
+        L.sws_slide1d_pair.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i32, _vp]
         L.sws_pool2d.restype = ctypes.c_int
         L.sws_pool2d.argtypes = [ctypes.c_int, _vp, _vp, _i64, _i64, _i64, _i64,
                                  _i32, _i32, _i32, _i32, _i32, _i32, _f32, _vp]
@@ -118,6 +120,24 @@ def sws_slide1d(op, x, w, scale=1.0, y=None, stream=None):
     _check(lib().sws_slide1d(op, x.data_ptr(), y.data_ptr(), rows, length, w, scale, _stream(stream)),
            "sws_slide1d")
     return y
+
+
+def sws_slide1d_pair(u, v, w, yu=None, yv=None, stream=None):
+    """u, v [..., len] -> (yu, yv) [..., len-w+1]: sliding window sum under the pair operator."""
+    _dev(u, "u")
+    _dev(v, "v")
+    if u.shape != v.shape:
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_slide1d_pair")
+    length = u.shape[-1]
+    rows = u.numel() // length if length else 0
+    lo = length - w + 1
+    if lo < 1 or w < 1:
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_slide1d_pair")
+    yu = _out(yu, tuple(u.shape[:-1]) + (lo,), u)
+    yv = _out(yv, tuple(u.shape[:-1]) + (lo,), u)
+    _check(lib().sws_slide1d_pair(u.data_ptr(), v.data_ptr(), yu.data_ptr(), yv.data_ptr(), rows, length, w,
+                                  _stream(stream)), "sws_slide1d_pair")
+    return yu, yv
 
 
 def sws_pool2d(op, x, kh, kw, sh=1, sw=1, ph=0, pw=0, scale=1.0, y=None, stream=None):

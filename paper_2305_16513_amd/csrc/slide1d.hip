@@ -422,6 +422,7 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
     int variant = g_opt.slide_variant;
     if (variant == 2 && w > kDirectMaxW) variant = 0;
     if (variant == 3 && (w < 2 || w > kScanMaxW)) variant = 0;
+    if (variant == 4) return launch_slide1d_generic(op, x, y, rows, len64, w, scale, s);   // generic-operator kernel (A/B)
     if (variant == 0) variant = (w == 1) ? 2 : (w <= kScanMaxW ? 3 : 1);
     if (variant == 1) return launch_slide1d_naive(op, x, y, rows, len64, w, scale, s);
     if (variant == 2) {

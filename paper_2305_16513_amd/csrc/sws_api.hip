@@ -85,6 +85,18 @@ sws_status sws_slide1d(sws_op op, const float *x, float *y, int64_t rows, int64_
     return from_hip(sws::launch_slide1d((int)op, x, y, rows, len, w, scale, (hipStream_t)stream));
 }
 
+sws_status sws_slide1d_pair(const float *u, const float *v, float *yu, float *yv, int64_t rows, int64_t len,
+                            int32_t w, void *stream)
+{
+    if (rows < 0 || len < 0 || w < 1) return SWS_ERR_INVALID_ARG;
+    if (len > kMaxDim || (int64_t)w > len) return SWS_ERR_INVALID_ARG;
+    int64_t n_in;
+    if (!mul3(rows, len, 1, &n_in)) return SWS_ERR_INVALID_ARG;
+    if (rows == 0) return SWS_OK;
+    if (!u || !v || !yu || !yv) return SWS_ERR_INVALID_ARG;
+    return from_hip(sws::launch_slide1d_pair(u, v, yu, yv, rows, len, w, (hipStream_t)stream));
+}
+
 sws_status sws_pool2d(sws_op op, const float *x, float *y, int64_t N, int64_t C, int64_t H, int64_t W,
                       int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
                       float scale, void *stream)

@@ -16,7 +16,7 @@ from dataclasses import dataclass, field
 
 import numpy as np
 
-SEED_BASE = 2305165130  # + config number 1..7
+SEED_BASE = 2305165130  # + config number 1..8
 
 
 @dataclass(frozen=True)
@@ -47,6 +47,9 @@ CONFIGS = {
     # Experiments section, second figure: a 51-tap kernel with dilation 8; one sequence whose
     # output size runs over DILATED_OUTPUT_SIZES, and a batched depthwise form that fills the device.
     7: Config(7, "exp_dilated_1d", (1, 4096, 65536), "uniform", (4096, 1, 51), 0.2, ("dwconv_k51_d8",)),
+
+    # Section 2.4: pairs (u, v) for the sliding window sum under the pair operator of Eq. 8.
+    8: Config(8, "pair_operator_1d", (16384, 16384), "pairs", (), 0.0, ("slide_pair_w16", "slide_pair_w255")),
 }
 
 FILTER_SIZES = (3, 5, 11, 17, 21, 29, 37, 49, 51)
@@ -67,6 +70,22 @@ def _draw(rng, shape, dist):
         raise ValueError(dist)
     a += np.float32(0.0)          # turns any -0.0 into +0.0
     return a
+
+
+def make_pairs(shape=None, seed_offset=0):
+    """(u, v) planes for configuration 8: u = +-(1 + 0.03 U[-1,1]) with one sign in five negative,
+    so that products of a few hundred factors stay in range; v ~ N(0,1)."""
+    shape = tuple(shape or CONFIGS[8].x_shape)
+    ss = np.random.SeedSequence(SEED_BASE + 8 + 1000 * seed_offset)
+    su, sg, sv = ss.spawn(3)
+    u = np.random.Generator(np.random.PCG64(su)).random(shape, dtype=np.float32)
+    u *= np.float32(0.06)
+    u += np.float32(0.97)
+    neg = np.random.Generator(np.random.PCG64(sg)).random(shape, dtype=np.float32) < np.float32(0.2)
+    np.negative(u, out=u, where=neg)
+    v = np.random.Generator(np.random.PCG64(sv)).standard_normal(shape, dtype=np.float32)
+    v += np.float32(0.0)
+    return u, v
 
 
 def check_clean(a):

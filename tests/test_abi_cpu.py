@@ -67,6 +67,20 @@ def test_slide1d_argument_checks(L):
     assert L.sws_slide1d(0, one, one, 2 ** 40, 2 ** 30, 3, 1.0, nul) == 1  # size overflow
 
 
+def test_slide1d_pair_argument_checks(L):
+    one = ctypes.c_void_p(16)
+    nul = ctypes.c_void_p(0)
+    assert L.sws_slide1d_pair(one, one, one, one, 0, 100, 3, nul) == 0        # no rows: nothing to do
+    assert L.sws_slide1d_pair(one, one, one, one, 1, 100, 0, nul) == 1        # w < 1
+    assert L.sws_slide1d_pair(one, one, one, one, 1, 100, 101, nul) == 1      # w > len
+    assert L.sws_slide1d_pair(one, one, one, one, -1, 100, 3, nul) == 1
+    assert L.sws_slide1d_pair(one, one, one, one, 1, 2 ** 31, 3, nul) == 1    # row too long for int32
+    for k in range(4):                                                       # any NULL plane with output
+        args = [one, one, one, one]
+        args[k] = nul
+        assert L.sws_slide1d_pair(*args, 1, 100, 3, nul) == 1
+
+
 def test_pool2d_argument_checks(L):
     one, nul = ctypes.c_void_p(16), ctypes.c_void_p(0)
     ok = (0, one, one, 0, 3, 8, 8, 3, 3, 1, 1, 1, 1, 1.0, nul)
