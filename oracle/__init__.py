@@ -14,7 +14,12 @@ from .ref import (  # noqa: F401
     conv1d,
     conv2d,
     pool2d,
+    PAD_EDGE,
+    PAD_IDENTITY,
+    PAD_MIRROR,
+    PAD_PERIODIC,
     slide1d,
+    slide1d_padded,
     slide1d_pair,
     threads,
 )

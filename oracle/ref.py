@@ -43,6 +43,9 @@ def _load():
         lib.sws_ref_pool2d.restype = ctypes.c_int
         lib.sws_ref_pool2d.argtypes = [ctypes.c_int, _fp, _dp, _dp, _i64, _i64, _i64, _i64,
                                        _i32, _i32, _i32, _i32, _i32, _i32, _f64]
+        lib.sws_ref_slide1d_padded.restype = ctypes.c_int
+        lib.sws_ref_slide1d_padded.argtypes = [ctypes.c_int, _fp, _dp, _dp, _i64, _i64, _i32, _i32, _i32,
+                                               ctypes.c_int, _f64]
         lib.sws_ref_slide1d_pair.restype = ctypes.c_int
         lib.sws_ref_slide1d_pair.argtypes = [_fp, _fp, _dp, _dp, _dp, _dp, _i64, _i64, _i32]
         lib.sws_ref_conv1d.restype = ctypes.c_int
@@ -89,6 +92,28 @@ def slide1d(op, x, w, scale=1.0):
     rc = _load().sws_ref_slide1d(op, _ptr_f(x), _ptr_d(y), _ptr_d(s), rows, length, w, float(scale))
     if rc:
         raise ValueError("sws_ref_slide1d rejected its arguments")
+    return y, s
+
+
+PAD_IDENTITY, PAD_MIRROR, PAD_PERIODIC, PAD_EDGE = 0, 1, 2, 3
+
+
+def slide1d_padded(op, x, w, pad_left, pad_right, mode, scale=1.0):
+    """x: [rows, len] float32 -> (y, abs_sum), each [rows, len+pad_left+pad_right-w+1] float64:
+    Eq. 3 over rows extended at both ends by the rule of `mode`."""
+    x = _f32(x)
+    if x.ndim == 1:
+        x = x[None, :]
+    rows, length = x.shape
+    lo = length + pad_left + pad_right - w + 1
+    if lo < 1:
+        raise ValueError("window longer than the extended row")
+    y = np.empty((rows, lo), np.float64)
+    s = np.empty((rows, lo), np.float64)
+    rc = _load().sws_ref_slide1d_padded(op, _ptr_f(x), _ptr_d(y), _ptr_d(s), rows, length, w, pad_left, pad_right,
+                                        mode, float(scale))
+    if rc:
+        raise ValueError("sws_ref_slide1d_padded rejected its arguments")
     return y, s
 
 

@@ -19,6 +19,10 @@
  *                    checked against an independent formulation.  Taps that
  *                    fall into the padding contribute the identity of the
  *                    operator (they are skipped).
+ *   sws_ref_slide1d_padded  Eq. 3 on rows extended at both ends (the boundary conditions
+ *                    named in Section 3: padding, mirroring, periodicity; plus edge
+ *                    replication).  Every window element's index is mapped back into
+ *                    the row by the rule of the mode, then combined as in Eq. 3.
  *   sws_ref_slide1d_pair  Eq. 3 with the pair operator of Section 2.4, Eq. 8:
  *                    (u_i, v_i) (+) (u_j, v_j) = (u_i*u_j, u_j*v_i + v_j), i older.
  *                    Non-commutative; folded strictly left to right.
@@ -249,6 +253,47 @@ int sws_ref_slide1d_pair(const float *u, const float *v, double *yu, double *yv,
             yv[r * lo + i] = V;
             if (mag_u) mag_u[r * lo + i] = fabs(U);
             if (mag_v) mag_v[r * lo + i] = MV;
+        }
+    }
+    return 0;
+}
+
+/* Eq. 3 over rows extended by pad_left / pad_right virtual elements.  mode: 0 = the identity of
+ * the operator (0 for ADD, -inf for MAX, +inf for MIN; such elements are skipped), 1 = mirror
+ * about the end elements without repeating them (x[-i] = x[i]), 2 = periodic (x[-i] = x[len-i]),
+ * 3 = the end element repeated.  y, abs_sum: rows*(len+pad_left+pad_right-w+1) doubles. */
+int sws_ref_slide1d_padded(int op, const float *x, double *y, double *abs_sum, int64_t rows, int64_t len,
+                           int32_t w, int32_t pad_left, int32_t pad_right, int mode, double scale)
+{
+    if (op < 0 || op > 2 || mode < 0 || mode > 3 || rows < 0 || len < 1 || w < 1 || pad_left < 0 || pad_right < 0)
+        return 1;
+    const int64_t lv = len + pad_left + pad_right, lo = lv - w + 1;
+    if (lo < 1) return 1;
+    if (mode == 1 && (pad_left > len - 1 || pad_right > len - 1)) return 1;
+    if (mode == 2 && (pad_left > len || pad_right > len)) return 1;
+    if (rows > 0 && (!x || !y)) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const float *xr = x + r * len;
+        for (int64_t i = 0; i < lo; ++i) {
+            double acc = 0.0, mag = 0.0;
+            int have = 0;
+            for (int32_t t = 0; t < w; ++t) {
+                int64_t p = i + t - pad_left;            /* index into the physical row, may be outside */
+                if (p < 0 || p >= len) {
+                    if (mode == 0) continue;             /* identity element: contributes nothing */
+                    if (mode == 1) p = p < 0 ? -p : 2 * (len - 1) - p;
+                    else if (mode == 2) p = p < 0 ? p + len : p - len;
+                    else p = p < 0 ? 0 : len - 1;
+                }
+                const double v = (double)xr[p];
+                acc = have ? combine(op, acc, v) : v;
+                have = 1;
+                mag += fabs(v);
+            }
+            if (!have) acc = op == REF_ADD ? 0.0 : (op == REF_MAX ? -INFINITY : INFINITY);
+            y[r * lo + i] = op == REF_ADD ? acc * scale : acc;
+            if (abs_sum) abs_sum[r * lo + i] = op == REF_ADD ? mag * fabs(scale) : mag;
         }
     }
     return 0;

@@ -563,3 +563,58 @@ def test_pair_full_window_of_gamma_sequence_is_the_dot_product(k):
     v = np.array(list(be) + [0.0], np.float32)
     _, yv, _, _ = oracle.slide1d_pair(u, v, k + 1)
     assert yv.shape == (1, 1) and yv[0, 0] == float(np.dot(al, be))
+
+
+# ----------------------------------------------------------------------------- P10
+# Boundary conditions (Section 3 names padding, mirroring and periodicity).
+def test_padded_hand_enumerated():
+    x = np.array([1, 2, 3], np.float32)
+    # extended rows by hand: mirror 3 2 | 1 2 3 | 2 1 ; periodic 2 3 | 1 2 3 | 1 2 ; edge 1 1 | 1 2 3 | 3 3
+    want = {oracle.PAD_MIRROR: [3, 2, 1, 2, 3, 2, 1], oracle.PAD_PERIODIC: [2, 3, 1, 2, 3, 1, 2],
+            oracle.PAD_EDGE: [1, 1, 1, 2, 3, 3, 3]}
+    for mode, ext in want.items():
+        y, _ = oracle.slide1d_padded(OP_ADD, x, 1, 2, 2, mode)
+        assert y[0].tolist() == ext
+        y, _ = oracle.slide1d_padded(OP_ADD, x, 3, 2, 2, mode)
+        assert y[0].tolist() == [sum(ext[i:i + 3]) for i in range(5)]
+        y, _ = oracle.slide1d_padded(OP_MAX, x, 2, 2, 2, mode)
+        assert y[0].tolist() == [max(ext[i:i + 2]) for i in range(6)]
+    y, m = oracle.slide1d_padded(OP_ADD, x, 3, 2, 1, oracle.PAD_IDENTITY, 0.5)      # 0 0 | 1 2 3 | 0
+    assert y[0].tolist() == [0.5, 1.5, 3.0, 2.5] and m[0].tolist() == [0.5, 1.5, 3.0, 2.5]
+    y, _ = oracle.slide1d_padded(OP_MAX, -x, 2, 2, 0, oracle.PAD_IDENTITY)          # -inf -inf | -1 -2 -3
+    assert y[0].tolist() == [-np.inf, -1.0, -1.0, -2.0]
+    y, _ = oracle.slide1d_padded(OP_MIN, x, 2, 0, 2, oracle.PAD_IDENTITY)           # 1 2 3 | +inf +inf
+    assert y[0].tolist() == [1.0, 2.0, 3.0, np.inf]
+
+
+@pytest.mark.parametrize("mode,np_mode", [(1, "reflect"), (2, "wrap"), (3, "edge"), (0, "constant")])
+@pytest.mark.parametrize("w,pl,pr", [(1, 0, 0), (3, 1, 1), (5, 4, 0), (8, 0, 7), (16, 15, 15), (31, 20, 9)])
+def test_padded_equals_plain_definition_on_an_explicitly_extended_row(mode, np_mode, w, pl, pr):
+    """numpy.pad writes the extended row out (a library routine as a second opinion on the index
+    rules); the unpadded oracle then runs over it."""
+    r = _rng(100 + w + pl)
+    x = r.standard_normal((3, 33), dtype=np.float32)
+    for op in (OP_ADD, OP_MAX, OP_MIN):
+        fill = {OP_ADD: 0.0, OP_MAX: -np.inf, OP_MIN: np.inf}[op]
+        kw = {"constant_values": fill} if mode == 0 else {}
+        ext = np.pad(x, ((0, 0), (pl, pr)), mode=np_mode, **kw).astype(np.float32)
+        y, m = oracle.slide1d_padded(op, x, w, pl, pr, mode, 0.25)
+        with np.errstate(invalid="ignore"):
+            ref, _ = oracle.slide1d(op, ext, w, 0.25)
+        assert np.array_equal(y, ref)
+
+
+def test_padded_without_padding_is_the_plain_sliding_sum_and_periodic_wraps():
+    r = _rng(101)
+    x = r.standard_normal((2, 50), dtype=np.float32)
+    for mode in range(4):
+        y, m = oracle.slide1d_padded(OP_ADD, x, 7, 0, 0, mode)
+        ref, mag = oracle.slide1d(OP_ADD, x, 7)
+        assert np.array_equal(y, ref) and np.array_equal(m, mag)
+    # periodic with pad_right = w - 1: one output per input, and their total is w times the row total
+    y, _ = oracle.slide1d_padded(OP_ADD, x, 7, 0, 6, oracle.PAD_PERIODIC)
+    assert y.shape == (2, 50) and np.allclose(y.sum(axis=1), 7 * x.astype(np.float64).sum(axis=1), atol=1e-12)
+    with pytest.raises(ValueError):
+        oracle.slide1d_padded(OP_ADD, x, 3, 50, 0, oracle.PAD_MIRROR)           # mirror reaches past the row
+    with pytest.raises(ValueError):
+        oracle.slide1d_padded(OP_ADD, x, 3, 0, 51, oracle.PAD_PERIODIC)
