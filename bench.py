@@ -154,7 +154,7 @@ def sweeps_table(torch, B, workloads, iters=20):
     plus a batched depthwise form that fills the device).  GB/s on algorithmic bytes, TFLOP/s on
     2*k FLOP per output; the vector-ALU peak without packed fp32 is 78.6 TFLOP/s."""
     g = lambda a: torch.from_numpy(a).cuda()
-    out = {"filter_sweep": {}, "dilated_single": {}, "dilated_batched": {}, "pair_operator": {}}
+    out = {"filter_sweep": {}, "dilated_single": {}, "dilated_batched": {}, "pair_operator": {}, "same_size_pooling": {}}
     c6 = workloads.CONFIGS[6]
     rows, length = c6.x_shape[0], c6.x_shape[2]
     x6 = g(workloads.make(6)[0])
@@ -203,6 +203,16 @@ def sweeps_table(torch, B, workloads, iters=20):
         out["pair_operator"]["w%d" % w] = {"ms": round(ms, 4), "GBps": round(nb / ms / 1e6, 1),
                                            "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
         del yu, yv
+    # one output per input: rows extended by (w-1)/2 mirrored elements at both ends (boundary rules, Section 3)
+    for op, opn in ((0, "avg"), (1, "max")):
+        for w in (15, 255):
+            y = torch.empty_like(u)
+            ms = time_launches(torch, lambda: B.sws_slide1d_padded(op, u, w, w // 2, w // 2, B.SWS_PAD_MIRROR, 1.0 / w, y=y),
+                               iters)
+            nb = 8 * u.numel()
+            out["same_size_pooling"]["%s_w%d_mirror" % (opn, w)] = {"ms": round(ms, 4), "GBps": round(nb / ms / 1e6, 1),
+                                                                    "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+            del y
     del u, v
     torch.cuda.empty_cache()
     return out

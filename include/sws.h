@@ -43,6 +43,15 @@ typedef enum {
  * MIN is the paper's example of another associative operator (Section 3). */
 typedef enum { SWS_OP_ADD = 0, SWS_OP_MAX = 1, SWS_OP_MIN = 2 } sws_op;
 
+/* Boundary conditions of an extended row (Section 3 names padding, mirroring and periodicity):
+ * what the virtual elements in front of x[0] and behind x[len-1] stand for. */
+typedef enum {
+    SWS_PAD_IDENTITY = 0,      /* the identity of the operator: 0 for ADD, -inf for MAX, +inf for MIN */
+    SWS_PAD_MIRROR = 1,        /* x[-i] = x[i], x[len-1+i] = x[len-1-i] (end elements not repeated) */
+    SWS_PAD_PERIODIC = 2,      /* x[-i] = x[len-i], x[len-1+i] = x[i-1] */
+    SWS_PAD_EDGE = 3           /* x[-i] = x[0], x[len-1+i] = x[len-1] */
+} sws_pad_mode;
+
 /* Sliding window sum, Section 2.2 Eq. 3, applied to `rows` independent sequences:
  *
  *   y[r, i] = scale * ( x[r,i] (+) x[r,i+1] (+) ... (+) x[r,i+w-1] ),   0 <= i <= len - w
@@ -54,6 +63,20 @@ typedef enum { SWS_OP_ADD = 0, SWS_OP_MAX = 1, SWS_OP_MIN = 2 } sws_op;
  * NULL while there is output, or a size overflows int64 / len exceeds 2^31-1. */
 sws_status sws_slide1d(sws_op op, const float *x, float *y, int64_t rows, int64_t len,
                        int32_t w, float scale, void *stream);
+
+/* The same sliding window sum over rows extended by pad_left virtual elements in front and
+ * pad_right behind, filled by the boundary rule `mode`:
+ *
+ *   y[r, i] = scale * ( xe[r,i] (+) ... (+) xe[r,i+w-1] ),   0 <= i <= len + pad_left + pad_right - w
+ *
+ * with xe the extended row.  pad_left = pad_right = (w-1)/2 with odd w gives one output per
+ * input ("same" pooling).  scale multiplies ADD results, padding included.
+ *   x : device, rows*len floats     y : device, rows*(len+pad_left+pad_right-w+1) floats
+ * Errors: as sws_slide1d, and INVALID_ARG if len < 1, a pad is negative, w exceeds the extended
+ * row, the mode is unknown, a MIRROR pad exceeds len-1 or a PERIODIC pad exceeds len. */
+sws_status sws_slide1d_padded(sws_op op, const float *x, float *y, int64_t rows, int64_t len,
+                              int32_t w, int32_t pad_left, int32_t pad_right, sws_pad_mode mode,
+                              float scale, void *stream);
 
 /* Sliding window sum (Eq. 3) under the pair operator of Section 2.4, Eq. 8 — the associative,
  * NON-commutative operator with which the paper writes a dot product as a prefix sum:

@@ -19,7 +19,7 @@ _lib = None
 
 _i64, _i32, _f32, _vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
 
-EXPORTS = ("sws_slide1d", "sws_slide1d_pair", "sws_pool2d", "sws_conv1d", "sws_conv2d", "sws_copy", "sws_out_len",
+EXPORTS = ("sws_slide1d", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_conv1d", "sws_conv2d", "sws_copy", "sws_out_len",
            "sws_status_string", "sws_set_option", "sws_version")
 
 
@@ -39,6 +39,8 @@ def lib():
         L = ctypes.CDLL(LIB_PATH)
         L.sws_slide1d.restype = ctypes.c_int
         L.sws_slide1d.argtypes = [ctypes.c_int, _vp, _vp, _i64, _i64, _i32, _f32, _vp]
+        L.sws_slide1d_padded.restype = ctypes.c_int
+        L.sws_slide1d_padded.argtypes = [ctypes.c_int, _vp, _vp, _i64, _i64, _i32, _i32, _i32, ctypes.c_int, _f32, _vp]
         L.sws_slide1d_pair.restype = ctypes.c_int
         L.sws_slide1d_pair.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i32, _vp]
         L.sws_pool2d.restype = ctypes.c_int
@@ -119,6 +121,23 @@ def sws_slide1d(op, x, w, scale=1.0, y=None, stream=None):
     y = _out(y, tuple(x.shape[:-1]) + (lo,), x)
     _check(lib().sws_slide1d(op, x.data_ptr(), y.data_ptr(), rows, length, w, scale, _stream(stream)),
            "sws_slide1d")
+    return y
+
+
+SWS_PAD_IDENTITY, SWS_PAD_MIRROR, SWS_PAD_PERIODIC, SWS_PAD_EDGE = 0, 1, 2, 3
+
+
+def sws_slide1d_padded(op, x, w, pad_left, pad_right, mode, scale=1.0, y=None, stream=None):
+    """x [..., len] -> y [..., len+pad_left+pad_right-w+1]: the rows are extended by the boundary rule `mode`."""
+    _dev(x, "x")
+    length = x.shape[-1]
+    rows = x.numel() // length if length else 0
+    lo = length + pad_left + pad_right - w + 1
+    if lo < 1 or w < 1 or pad_left < 0 or pad_right < 0:
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_slide1d_padded")
+    y = _out(y, tuple(x.shape[:-1]) + (lo,), x)
+    _check(lib().sws_slide1d_padded(op, x.data_ptr(), y.data_ptr(), rows, length, w, pad_left, pad_right, mode,
+                                    scale, _stream(stream)), "sws_slide1d_padded")
     return y
 
 

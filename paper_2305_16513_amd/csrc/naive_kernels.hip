@@ -9,11 +9,13 @@ namespace {
 
 constexpr int kThreads = 256;
 
-// Section 2.2, Eq. 3: y[r,i] = x[r,i] (+) ... (+) x[r,i+w-1], left to right.
+// Section 2.2, Eq. 3: y[r,i] = x[r,i] (+) ... (+) x[r,i+w-1], left to right, over the row
+// extended by pad_left elements in front (boundary rule `pad_mode`); lo outputs per row.
 template <int OP>
 __global__ __launch_bounds__(kThreads) void slide_naive_kernel(const float *__restrict__ x,
                                                                float *__restrict__ y, int64_t rows,
-                                                               int len, int lo, int w, float scale)
+                                                               int len, int lo, int w, int pad_left,
+                                                               int pad_mode, float scale)
 {
     using O = Op<OP>;
     const int64_t total = rows * (int64_t)lo;
@@ -21,9 +23,12 @@ __global__ __launch_bounds__(kThreads) void slide_naive_kernel(const float *__re
          o += (int64_t)gridDim.x * kThreads) {
         const int64_t r = o / lo;
         const int i = (int)(o - r * lo);
-        const float *xr = x + r * (int64_t)len + i;
-        float acc = xr[0];
-        for (int j = 1; j < w; ++j) acc = O::f(acc, xr[j]);
+        const float *xr = x + r * (int64_t)len;
+        float acc = O::id();
+        for (int j = 0; j < w; ++j) {
+            const int src = pad_src(i + j, len, pad_left, pad_mode);
+            acc = O::f(acc, src >= 0 ? xr[src] : O::id());
+        }
         if (OP == SWS_OP_ADD) acc *= scale;
         y[o] = acc;
     }
@@ -131,22 +136,22 @@ int grid_for(int64_t total)
 }  // namespace
 
 hipError_t launch_slide1d_naive(int op, const float *x, float *y, int64_t rows, int64_t len, int32_t w,
-                                float scale, hipStream_t s)
+                                int32_t pad_left, int32_t pad_right, int pad_mode, float scale, hipStream_t s)
 {
-    const int lo = (int)(len - w + 1);
+    const int lo = (int)(len + pad_left + pad_right - w + 1);
     const int grid = grid_for(rows * lo);
     switch (op) {
     case SWS_OP_ADD:
         hipLaunchKernelGGL(slide_naive_kernel<SWS_OP_ADD>, dim3(grid), dim3(kThreads), 0, s, x, y, rows,
-                           (int)len, lo, w, scale);
+                           (int)len, lo, w, pad_left, pad_mode, scale);
         break;
     case SWS_OP_MAX:
         hipLaunchKernelGGL(slide_naive_kernel<SWS_OP_MAX>, dim3(grid), dim3(kThreads), 0, s, x, y, rows,
-                           (int)len, lo, w, scale);
+                           (int)len, lo, w, pad_left, pad_mode, scale);
         break;
     default:
         hipLaunchKernelGGL(slide_naive_kernel<SWS_OP_MIN>, dim3(grid), dim3(kThreads), 0, s, x, y, rows,
-                           (int)len, lo, w, scale);
+                           (int)len, lo, w, pad_left, pad_mode, scale);
         break;
     }
     return hipGetLastError();

@@ -167,13 +167,19 @@ template <> struct SegStep<SWS_OP_MIN> {
     }
 };
 
-template <int OP, int C>
+template <int OP, int C, bool PADDED>
 __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__restrict__ x,
                                                               float *__restrict__ y, int len, int lo, int S,
                                                               float scale, int tiles_per_row, int tout,
                                                               int group, int64_t n_tiles, int64_t n_units,
-                                                              int flags)
+                                                              int flags, int pad_left_arg, int pad_mode_arg,
+                                                              int lv_arg)
 {
+    // The row the windows slide over is the physical row of `len` elements extended to `lv`
+    // (pad_left in front, the rest behind) by the boundary rule pad_mode; lo = lv - S outputs.
+    // The unpadded instantiation sees constants, so the common path carries none of this.
+    const int pad_left = PADDED ? pad_left_arg : 0, pad_mode = PADDED ? pad_mode_arg : SWS_PAD_IDENTITY;
+    const int lv = PADDED ? lv_arg : len;
     using O = Op<OP>;
     using G = SegStep<OP>;
     static_assert(C == 16, "the LDS layout assumes 16-element chunks");
@@ -246,10 +252,11 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
         const int t0 = t * tout - (aligned ? (int)((r * lo) & 15) : 0);
         const int qlo = t0 < 0 ? -t0 : 0;
         // tile-relative bases: uniform 64-bit arithmetic once, 32-bit lane offsets afterwards
-        const float *xt = xr + t0;
+        const float *xt = xr + (t0 - pad_left);
         float *yt = y + r * (int64_t)lo + t0;
-        // ---- stage the tile: coalesced strips -> LDS, identity outside the row
-        if (t0 >= 0 && t0 <= len - N) {
+        // ---- stage the tile: coalesced strips -> LDS; boundary rule in the padding, identity
+        //      outside the extended row
+        if (t0 - pad_left >= 0 && t0 - pad_left <= len - N) {
 #pragma unroll
             for (int j = 0; j < NS; ++j) {
                 const int q = j * 256 + 4 * lane;
@@ -259,13 +266,14 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
 #pragma unroll
             for (int j = 0; j < NS; ++j) {
                 const int q = j * 256 + 4 * lane;
-                v4f g;
-                const int p = t0 + q;
-                g.x = (p + 0 >= 0 && p + 0 < len) ? xr[p + 0] : O::id();
-                g.y = (p + 1 >= 0 && p + 1 < len) ? xr[p + 1] : O::id();
-                g.z = (p + 2 >= 0 && p + 2 < len) ? xr[p + 2] : O::id();
-                g.w = (p + 3 >= 0 && p + 3 < len) ? xr[p + 3] : O::id();
-                *(v4f *)(A + strip_pos + 256 * j) = g;
+                float e4[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int e = t0 + q + c;        // element of the extended row
+                    const int src = (e >= 0 && e < lv) ? pad_src(e, len, pad_left, pad_mode) : -1;
+                    e4[c] = src >= 0 ? xr[src] : O::id();
+                }
+                *(v4f *)(A + strip_pos + 256 * j) = (v4f){e4[0], e4[1], e4[2], e4[3]};
             }
         }
         wave_lds_sync();
@@ -372,7 +380,7 @@ hipError_t launch_direct(const float *x, float *y, int64_t rows, int len, int lo
 // 8 = force it off.
 template <int OP>
 hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, int w, float scale,
-                       hipStream_t s)
+                       int pad_left, int pad_mode, int lv, hipStream_t s)
 {
     constexpr int C = 16, N = kWave * C;
     const int S = w - 1;
@@ -405,8 +413,12 @@ hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, 
     const int64_t n_units = (n_tiles + g - 1) / g;
     const int64_t grid = remap ? xcd_grid(n_units) : n_units;
     if (grid > 2147483647LL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((slide_scan_kernel<OP, C>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
-                       S, scale, tiles, tout, (int)g, n_tiles, n_units, flags);
+    if (lv != len)
+        hipLaunchKernelGGL((slide_scan_kernel<OP, C, true>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
+                           S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, pad_left, pad_mode, lv);
+    else
+        hipLaunchKernelGGL((slide_scan_kernel<OP, C, false>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
+                           S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, 0, 0, len);
     return hipGetLastError();
 }
 
@@ -416,15 +428,17 @@ constexpr int kScanMaxW = kWave * 16 - 64 + 1;      // leaves at least 64 output
 }  // namespace
 
 hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_t len64, int32_t w,
-                          float scale, hipStream_t s)
+                          int32_t pad_left, int32_t pad_right, int pad_mode, float scale, hipStream_t s)
 {
-    const int len = (int)len64, lo = (int)(len64 - w + 1);
+    const int len = (int)len64, lv = (int)(len64 + pad_left + pad_right), lo = lv - w + 1;
+    const bool padded = pad_left != 0 || pad_right != 0;
     int variant = g_opt.slide_variant;
+    if ((variant == 2 || variant == 4) && padded) variant = 0;      // those kernels know no boundary rule
     if (variant == 2 && w > kDirectMaxW) variant = 0;
     if (variant == 3 && (w < 2 || w > kScanMaxW)) variant = 0;
     if (variant == 4) return launch_slide1d_generic(op, x, y, rows, len64, w, scale, s);   // generic-operator kernel (A/B)
-    if (variant == 0) variant = (w == 1) ? 2 : (w <= kScanMaxW ? 3 : 1);
-    if (variant == 1) return launch_slide1d_naive(op, x, y, rows, len64, w, scale, s);
+    if (variant == 0) variant = (w == 1) ? (padded ? 1 : 2) : (w <= kScanMaxW ? 3 : 1);
+    if (variant == 1) return launch_slide1d_naive(op, x, y, rows, len64, w, pad_left, pad_right, pad_mode, scale, s);
     if (variant == 2) {
         switch (op) {
         case SWS_OP_ADD: return launch_direct<SWS_OP_ADD>(x, y, rows, len, lo, w, scale, s);
@@ -433,9 +447,9 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
         }
     }
     switch (op) {
-    case SWS_OP_ADD: return launch_scan<SWS_OP_ADD>(x, y, rows, len, lo, w, scale, s);
-    case SWS_OP_MAX: return launch_scan<SWS_OP_MAX>(x, y, rows, len, lo, w, scale, s);
-    default: return launch_scan<SWS_OP_MIN>(x, y, rows, len, lo, w, scale, s);
+    case SWS_OP_ADD: return launch_scan<SWS_OP_ADD>(x, y, rows, len, lo, w, scale, pad_left, pad_mode, lv, s);
+    case SWS_OP_MAX: return launch_scan<SWS_OP_MAX>(x, y, rows, len, lo, w, scale, pad_left, pad_mode, lv, s);
+    default: return launch_scan<SWS_OP_MIN>(x, y, rows, len, lo, w, scale, pad_left, pad_mode, lv, s);
     }
 }
 

@@ -82,7 +82,24 @@ sws_status sws_slide1d(sws_op op, const float *x, float *y, int64_t rows, int64_
     if (!mul3(rows, len, 1, &n_in)) return SWS_ERR_INVALID_ARG;
     if (rows == 0) return SWS_OK;
     if (!x || !y) return SWS_ERR_INVALID_ARG;
-    return from_hip(sws::launch_slide1d((int)op, x, y, rows, len, w, scale, (hipStream_t)stream));
+    return from_hip(sws::launch_slide1d((int)op, x, y, rows, len, w, 0, 0, SWS_PAD_IDENTITY, scale, (hipStream_t)stream));
+}
+
+sws_status sws_slide1d_padded(sws_op op, const float *x, float *y, int64_t rows, int64_t len, int32_t w,
+                              int32_t pad_left, int32_t pad_right, sws_pad_mode mode, float scale, void *stream)
+{
+    if (!valid_op((int)op) || rows < 0 || len < 1 || w < 1 || pad_left < 0 || pad_right < 0) return SWS_ERR_INVALID_ARG;
+    if ((int)mode < SWS_PAD_IDENTITY || (int)mode > SWS_PAD_EDGE) return SWS_ERR_INVALID_ARG;
+    const int64_t lv = len + pad_left + pad_right;
+    if (lv > kMaxDim || (int64_t)w > lv) return SWS_ERR_INVALID_ARG;
+    if (mode == SWS_PAD_MIRROR && (pad_left > len - 1 || pad_right > len - 1)) return SWS_ERR_INVALID_ARG;
+    if (mode == SWS_PAD_PERIODIC && (pad_left > len || pad_right > len)) return SWS_ERR_INVALID_ARG;
+    int64_t n_out;
+    if (!mul3(rows, lv, 1, &n_out)) return SWS_ERR_INVALID_ARG;
+    if (rows == 0) return SWS_OK;
+    if (!x || !y) return SWS_ERR_INVALID_ARG;
+    return from_hip(sws::launch_slide1d((int)op, x, y, rows, len, w, pad_left, pad_right, (int)mode, scale,
+                                        (hipStream_t)stream));
 }
 
 sws_status sws_slide1d_pair(const float *u, const float *v, float *yu, float *yv, int64_t rows, int64_t len,

@@ -42,6 +42,20 @@ template <> struct Op<SWS_OP_MIN> {
     static __device__ __forceinline__ float f(float a, float b) { return __builtin_fminf(a, b); }
 };
 
+// Boundary conditions of a row extended by pad_left virtual elements in front (and more behind):
+// the physical index that virtual element e stands for, or -1 for the operator's identity.
+// mode: SWS_PAD_IDENTITY, SWS_PAD_MIRROR (x[-i] = x[i]), SWS_PAD_PERIODIC (x[-i] = x[len-i]),
+// SWS_PAD_EDGE (the end element repeated).  The caller keeps e inside the extended row.
+__device__ __forceinline__ int pad_src(int e, int len, int pad_left, int mode)
+{
+    const int p = e - pad_left;
+    if (p >= 0 && p < len) return p;
+    if (mode == SWS_PAD_IDENTITY) return -1;
+    if (mode == SWS_PAD_MIRROR) return p < 0 ? -p : 2 * (len - 1) - p;
+    if (mode == SWS_PAD_PERIODIC) return p < 0 ? p + len : p - len;
+    return p < 0 ? 0 : len - 1;
+}
+
 // Workgroups are dealt round-robin to the 8 XCDs.  This maps blockIdx so that each XCD
 // (one L2) walks a contiguous range of work units, keeping a tile's halo re-read in the
 // L2 that fetched it.  Returns an id in [0, n_units) or -1 for the padding blocks.
@@ -56,7 +70,7 @@ inline int64_t xcd_grid(int64_t n_units) { return ((n_units + kXcd - 1) / kXcd) 
 
 hipError_t launch_copy(const float *src, float *dst, int64_t n, hipStream_t s);
 hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_t len, int32_t w,
-                          float scale, hipStream_t s);
+                          int32_t pad_left, int32_t pad_right, int pad_mode, float scale, hipStream_t s);
 // Generic-operator kernels (slide_generic.hip): the pair operator, and +, max, min as a cross-check.
 hipError_t launch_slide1d_pair(const float *u, const float *v, float *yu, float *yv, int64_t rows, int64_t len,
                                int32_t w, hipStream_t s);
@@ -79,7 +93,7 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
 
 // Direct-evaluation fallbacks (naive_kernels.hip).
 hipError_t launch_slide1d_naive(int op, const float *x, float *y, int64_t rows, int64_t len, int32_t w,
-                                float scale, hipStream_t s);
+                                int32_t pad_left, int32_t pad_right, int pad_mode, float scale, hipStream_t s);
 hipError_t launch_pool2d_naive(int op, const float *x, float *y, int64_t planes, int64_t H, int64_t W,
                                int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
                                int32_t ph, int32_t pw, float scale, hipStream_t s);

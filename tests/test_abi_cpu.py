@@ -67,6 +67,22 @@ def test_slide1d_argument_checks(L):
     assert L.sws_slide1d(0, one, one, 2 ** 40, 2 ** 30, 3, 1.0, nul) == 1  # size overflow
 
 
+def test_slide1d_padded_argument_checks(L):
+    one = ctypes.c_void_p(16)
+    nul = ctypes.c_void_p(0)
+    f = L.sws_slide1d_padded
+    assert f(0, one, one, 0, 100, 3, 1, 1, 0, 1.0, nul) == 0               # no rows: nothing to do
+    assert f(0, one, one, 1, 100, 3, -1, 1, 0, 1.0, nul) == 1              # negative pad
+    assert f(0, one, one, 1, 100, 3, 1, 1, 4, 1.0, nul) == 1               # unknown mode
+    assert f(0, one, one, 1, 100, 103, 1, 1, 0, 1.0, nul) == 1             # w longer than the extended row
+    assert f(0, one, one, 1, 100, 3, 100, 0, 1, 1.0, nul) == 1             # mirror pad reaches past the row
+    assert f(0, one, one, 1, 100, 3, 0, 101, 2, 1.0, nul) == 1             # periodic pad longer than the row
+    assert f(0, one, one, 1, 0, 1, 1, 1, 0, 1.0, nul) == 1                 # empty rows cannot be extended
+    assert f(5, one, one, 1, 100, 3, 1, 1, 0, 1.0, nul) == 1               # unknown op
+    assert f(0, nul, one, 1, 100, 3, 1, 1, 0, 1.0, nul) == 1               # NULL with output
+    assert f(0, one, one, 1, 2 ** 31 - 10, 3, 100000, 0, 3, 1.0, nul) == 1  # extended row too long for int32
+
+
 def test_slide1d_pair_argument_checks(L):
     one = ctypes.c_void_p(16)
     nul = ctypes.c_void_p(0)
