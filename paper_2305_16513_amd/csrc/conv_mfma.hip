@@ -37,6 +37,7 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 
 struct ConvGeom {
     int Cin, H, W, Cout, Ho, Wo, kh, kw, ph, pw;
+    int sh, sw;                                       // strides (the channel-fastest kernel only)
     int mode_b;                                       // 0: flat tiles over rows, 1: column tiles of one row
     int NP;                                           // output positions per workgroup
     int Wt, NRows, CP;                                // staged row pitch, staged rows, channel pitch in LDS
@@ -255,11 +256,11 @@ __global__ __launch_bounds__(WAVES * 64, 2) void conv2d_mfma_kernel(const float 
 // Staging plan of the input tile, computed on the host and passed by value: segment i (one
 // staged row of one channel, 64 columns wide) packs its channel, row and chunk into e[i].  Wavefront w moves segments w, w+8, ...; the lookups are scalar loads.
 struct SegPlan {
-    unsigned int e[64];                               // channel | row << 8 | chunk << 16
+    unsigned int e[128];                              // channel | row << 8 | chunk << 16
 };
 
 // (the second launch bound is wavefronts per SIMD: two workgroups per compute unit)
-template <int KTT, int WAVES, int NB>
+template <int KTT, int WAVES, int NB, int SEG>
 __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c8_kernel(const float *__restrict__ x,
                                                                        const float *__restrict__ wgt,
                                                                        float *__restrict__ y, ConvGeom g,
@@ -268,7 +269,7 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
     // NB blocks of 8 input channels are staged per barrier pair (NB > 1 for few taps, where one
     // block is too little matrix work between two barriers).
     constexpr int CIB = 8, XP = 12;
-    constexpr int MAXSEG = NB == 1 ? 64 : 32;         // segments of one channel block (checked by the host)
+    constexpr int MAXSEG = SEG;                       // segments of one channel block (checked by the host)
     constexpr int XS = (MAXSEG + WAVES - 1) / WAVES;  // staged-input registers per lane and channel block
     constexpr int KTMAX = KTT > 0 ? KTT : 9;          // staged-weight registers per lane and channel block
     extern __shared__ __attribute__((aligned(16))) float lds[];
@@ -297,7 +298,7 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
         oh_first = p_base / g.Wo;
         ow_first = 0;
     }
-    const int row0 = oh_first - g.ph, col0 = ow_first - g.pw;
+    const int row0 = oh_first * g.sh - g.ph, col0 = ow_first * g.sw - g.pw;
 
     // my position
     int oh, ow;
@@ -315,7 +316,7 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
             pok = p < g.Ho * g.Wo;
         }
     }
-    const int b_lane = (pok ? (oh - oh_first) * g.Wt + (ow - ow_first) : 0) * XP + 4 * half;
+    const int b_lane = (pok ? (oh - oh_first) * g.sh * g.Wt + (ow - ow_first) * g.sw : 0) * XP + 4 * half;
     const int a_lane = (wm * 32 + l32) * XP + 4 * half;
 
     v16f acc;
@@ -421,17 +422,17 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
 bool plan(ConvGeom &g, int NP, int CIB, int xslots_total, int64_t N, int64_t *n_units, size_t *lds_bytes)
 {
     g.NP = NP;
-    if (g.Wo + g.kw - 1 <= 192) {                     // mode A: flat tiles, full-width rows
+    if ((g.Wo - 1) * g.sw + g.kw <= 192) {            // mode A: flat tiles, full-width rows
         g.mode_b = 0;
-        g.Wt = g.Wo + g.kw - 1;
+        g.Wt = (g.Wo - 1) * g.sw + g.kw;
         // output rows a tile can touch (tiles of whole rows always start on a row)
         const int rows = (g.NP % g.Wo == 0) ? g.NP / g.Wo : (g.NP + g.Wo - 2) / g.Wo + 1;
-        g.NRows = (rows < g.Ho ? rows : g.Ho) + g.kh - 1;
+        g.NRows = ((rows < g.Ho ? rows : g.Ho) - 1) * g.sh + g.kh;
         g.tiles_c = 1;
         g.tiles_per_img = (g.Ho * g.Wo + g.NP - 1) / g.NP;
     } else {                                          // mode B: column tiles of single rows
         g.mode_b = 1;
-        g.Wt = g.NP + g.kw - 1;
+        g.Wt = (g.NP - 1) * g.sw + g.kw;
         g.NRows = g.kh;
         g.tiles_c = (g.Wo + g.NP - 1) / g.NP;
         g.tiles_per_img = g.Ho * g.tiles_c;
@@ -444,8 +445,9 @@ bool plan(ConvGeom &g, int NP, int CIB, int xslots_total, int64_t N, int64_t *n_
     *n_units = N * g.co_blocks * g.tiles_per_img;
     *lds_bytes = 4 * ((size_t)CIB * g.CP + (size_t)kCoTile * (CIB * g.kh * g.kw + 2));
     const int nseg = CIB * g.NRows * g.CH;
-    return *lds_bytes <= 64 * 1024 && nseg <= xslots_total && kCoTile * (CIB * g.kh * g.kw / 4) <= 2304 &&
-           (int64_t)g.Cin * g.H * g.W < 2147483647LL;
+    // (the channel-fastest kernel passes xslots_total = 1 << 30 and checks its own LDS layout)
+    const bool fits = xslots_total == (1 << 30) || (*lds_bytes <= 64 * 1024 && nseg <= xslots_total);
+    return fits && kCoTile * (CIB * g.kh * g.kw / 4) <= 2304 && (int64_t)g.Cin * g.H * g.W < 2147483647LL;
 }
 
 template <int WAVES, int MB, int NBW, int CIB>
@@ -461,20 +463,21 @@ hipError_t launch(const float *x, const float *wgt, float *y, const ConvGeom &g,
 
 }  // namespace
 
-// Stride-1, undilated, groups = 1 convolution on the matrix cores.  *taken = false means the
+// Undilated, groups = 1 convolution on the matrix cores (strides in the channel-fastest kernel).  *taken = false means the
 // shape is outside what this kernel covers and nothing was launched.
 hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
-                              int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t ph,
-                              int32_t pw, hipStream_t s, bool *taken)
+                              int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh,
+                              int32_t sw, int32_t ph, int32_t pw, hipStream_t s, bool *taken)
 {
     *taken = false;
+    const bool strided = sh != 1 || sw != 1;
     const int KT = kh * kw;
     // channel blocks of 16 (or 4 for big kernels / odd channel counts) must divide Cin
     const int CIB = (KT <= 9 && Cin % 16 == 0) ? 16 : ((KT <= 36 && Cin % 4 == 0) ? 4 : 0);
     if (CIB == 0 || Ho * Wo > 2147483647LL / 2 || Cout * Cin * KT > 2147483647LL / 2) return hipSuccess;
     ConvGeom g;
     g.Cin = (int)Cin; g.H = (int)H; g.W = (int)W; g.Cout = (int)Cout; g.Ho = (int)Ho; g.Wo = (int)Wo;
-    g.kh = kh; g.kw = kw; g.ph = ph; g.pw = pw;
+    g.kh = kh; g.kw = kw; g.ph = ph; g.pw = pw; g.sh = sh; g.sw = sw;
     int64_t units = 0;
     size_t lds = 0;
     // preferred: channel-fastest tiles with 128-bit operand reads (kh*kw <= 9, Cin % 8 == 0)
@@ -488,7 +491,9 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
             ConvGeom t = g;
             if (!plan(t, 16 * wv, 16, 1 << 30, N, &units, &lds)) continue;
             const int xfl = (t.NRows * t.Wt * 12 + 3) / 4 * 4;
-            if (8 * t.NRows * t.CH > 64 || t.NRows >= 256 || 4 * ((size_t)xfl + (size_t)KT * kCoTile * 12) > 64 * 1024)
+            // staging plan: up to 64 row segments per channel block, 128 with 8 wavefronts
+            if (8 * t.NRows * t.CH > (wv == 8 ? 128 : 64) || t.NRows >= 256 ||
+                4 * ((size_t)xfl + (size_t)KT * kCoTile * 12) > 64 * 1024)
                 continue;
             const int64_t cost = ((units + 511) / 512) * wv;
             if (best_w == 0 || cost < best_cost) { best_w = wv; best_cost = cost; }
@@ -502,36 +507,42 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
                              g_opt.conv2d_variant != 5;
             const size_t lds8 = (nb4 ? 4 : 1) * lds1;
             g.CP = xfloats;
+            const bool seg128 = 8 * g.NRows * g.CH > 64;      // only reached with 8 wavefronts
             SegPlan sp;
-            for (int i = 0; i < 64; ++i) {
+            for (int i = 0; i < 128; ++i) {
                 const int ci = i / (g.NRows * g.CH), r2 = i % (g.NRows * g.CH);
                 sp.e[i] = (unsigned)(ci < 8 ? ci : 0) | (unsigned)(r2 / g.CH) << 8 | (unsigned)(r2 % g.CH) << 16;
             }
             const dim3 grid((unsigned)g.tiles_per_img, (unsigned)g.co_blocks, (unsigned)N);
             *taken = true;
-#define SWS_C8(KTT, WV, NB)                                                                                     \
-    hipLaunchKernelGGL((conv2d_mfma_c8_kernel<KTT, WV, NB>), grid, dim3(WV * 64), lds8, s, x, wgt, y, g, sp)
-#define SWS_C8_W(KTT, NB)                                                                                       \
+#define SWS_C8(KTT, WV, NB, SEG)                                                                                \
+    hipLaunchKernelGGL((conv2d_mfma_c8_kernel<KTT, WV, NB, SEG>), grid, dim3(WV * 64), lds8, s, x, wgt, y, g, sp)
+#define SWS_C8_W(KTT, NB, SEG)                                                                                  \
     switch (best_w) {                                                                                           \
-    case 8: SWS_C8(KTT, 8, NB); break;                                                                          \
-    case 10: SWS_C8(KTT, 10, NB); break;                                                                        \
-    case 12: SWS_C8(KTT, 12, NB); break;                                                                        \
-    default: SWS_C8(KTT, 14, NB); break;                                                                        \
+    case 8: SWS_C8(KTT, 8, NB, SEG); break;                                                                     \
+    case 10: SWS_C8(KTT, 10, NB, SEG); break;                                                                   \
+    case 12: SWS_C8(KTT, 12, NB, SEG); break;                                                                   \
+    default: SWS_C8(KTT, 14, NB, SEG); break;                                                                   \
     }
-            if (KT == 9 && kw == 3) {
-                SWS_C8_W(9, 1)
+            if (seg128) {                                 // tall input tiles (strided convolution)
+                if (KT == 9 && kw == 3) SWS_C8(9, 8, 1, 128);
+                else if (KT == 3 && kw == 3) SWS_C8(3, 8, 1, 128);
+                else SWS_C8(0, 8, 1, 128);
+            } else if (KT == 9 && kw == 3) {
+                SWS_C8_W(9, 1, 64)
             } else if (nb4) {
-                SWS_C8_W(3, 4)
+                SWS_C8_W(3, 4, 32)
             } else if (KT == 3 && kw == 3) {
-                SWS_C8_W(3, 1)
+                SWS_C8_W(3, 1, 64)
             } else {
-                SWS_C8_W(0, 1)
+                SWS_C8_W(0, 1, 64)
             }
 #undef SWS_C8_W
 #undef SWS_C8
             return hipGetLastError();
         }
     }
+    if (strided) return hipSuccess;                   // the scalar-read kernels below are stride-1 only
     if (!plan(g, 128, CIB, CIB == 16 ? 128 : 64, N, &units, &lds)) return hipSuccess;
     *taken = true;
     if (g_opt.conv2d_variant == 3) {                  // 4 wavefronts, two channel blocks each (A/B)

@@ -7,9 +7,9 @@ hipError_t launch_conv2d(const float *x, const float *wgt, float *y, int64_t N, 
                          int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh,
                          int32_t sw, int32_t ph, int32_t pw, hipStream_t s)
 {
-    if (g_opt.conv2d_variant != 1 && sh == 1 && sw == 1) {
+    if (g_opt.conv2d_variant != 1) {
         bool taken = false;
-        const hipError_t e = launch_conv2d_mfma(x, wgt, y, N, Cin, H, W, Cout, Ho, Wo, kh, kw, ph, pw, s, &taken);
+        const hipError_t e = launch_conv2d_mfma(x, wgt, y, N, Cin, H, W, Cout, Ho, Wo, kh, kw, sh, sw, ph, pw, s, &taken);
         if (taken) return e;
     }
     return launch_conv2d_naive(x, wgt, y, N, Cin, H, W, Cout, Ho, Wo, kh, kw, sh, sw, ph, pw, s);

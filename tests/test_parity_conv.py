@@ -154,6 +154,29 @@ def test_conv2d_kernel_selection_paths(B, cin, cout, kh, kw, h, w_, ph, pw):
     _c2(B, x, w, 1, 1, ph, pw, what=str((cin, cout, kh, kw, h, w_)))
 
 
+@pytest.mark.parametrize("cin,cout,kh,kw,h,w_,sh,sw,ph,pw", [
+    (64, 64, 3, 3, 56, 56, 2, 2, 1, 1),     # ResNet-style downsampling: tall input tiles (128-segment staging plan)
+    (64, 128, 1, 1, 56, 56, 2, 2, 0, 0),    # 1 x 1 projection with stride 2
+    (32, 64, 3, 3, 33, 47, 2, 1, 1, 0),     # stride along H only, ragged sizes
+    (16, 16, 3, 3, 20, 300, 1, 3, 1, 1),    # wide rows (column tiles), stride 3 along W
+    (8, 24, 2, 2, 64, 64, 2, 2, 0, 0),      # non-overlapping 2 x 2 patches
+    (64, 64, 3, 3, 112, 112, 2, 2, 1, 1),   # input tile too tall for the staging plan: direct evaluation
+])
+def test_conv2d_strided(B, cin, cout, kh, kw, h, w_, sh, sw, ph, pw):
+    r = _rng(cin + cout + kh * 11 + h + sh * 3 + sw)
+    x = r.standard_normal((2, cin, h, w_), dtype=np.float32)
+    w = (r.standard_normal((cout, cin, kh, kw), dtype=np.float32) * np.sqrt(2.0 / (cin * kh * kw))).astype(np.float32)
+    _c2(B, x, w, sh, sw, ph, pw, what=str((cin, cout, kh, kw, h, w_, sh, sw, ph, pw)))
+
+
+@pytest.mark.parametrize("stride,k,pad", [(2, 3, 1), (3, 5, 2), (2, 1, 0), (4, 9, 4)])
+def test_conv1d_dense_strided(B, stride, k, pad):
+    r = _rng(stride * 10 + k)
+    x = r.standard_normal((3, 32, 1500), dtype=np.float32)
+    w = (r.standard_normal((48, 32, k), dtype=np.float32) * np.sqrt(2.0 / (32 * k))).astype(np.float32)
+    _c1(B, x, w, stride=stride, pad=pad, what="dense stride=%d k=%d" % (stride, k))
+
+
 @pytest.mark.parametrize("variant", [1, 3, 8, 10, 12, 14])
 def test_conv2d_variants_agree_with_oracle(B, variant):
     """The direct-evaluation kernel (1), the 4-wavefront scalar-read matrix kernel (3), and the
