@@ -207,6 +207,8 @@ hipError_t dispatch_band(const float *x, float *y, int64_t planes, int H, int W,
     SWS_BAND(5, 5, 1, 1, 2);
     SWS_BAND(5, 5, 1, 1, 0);
     SWS_BAND(7, 7, 1, 1, 3);
+    SWS_BAND(9, 9, 1, 1, 4);
+    SWS_BAND(13, 13, 1, 1, 6);
 #undef SWS_BAND
     *taken = false;
     return hipSuccess;
