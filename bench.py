@@ -93,7 +93,30 @@ def ops_table(torch, B, workloads, iters=20):
             return sets[state["i"]]
         return sets[0], pick
 
-    def record(name, launch, make_args, nbytes, flops=0.0):
+    def graph_ms(launch, args, n=20, replays=5):
+        """Mean duration of one launch inside a HIP graph of n back-to-back launches: what the
+        small operators cost once the host's launch path (about 10 us from Python) is out of the way."""
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            launch(*args)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            for _ in range(n):
+                launch(*args)
+        gr.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(replays):
+            gr.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (n * replays)
+
+    def record(name, launch, make_args, nbytes, flops=0.0, graph=False):
         first, pick = rotate(make_args, nbytes)
         warm = time_launches(torch, lambda: launch(*first), iters)
         cold = time_launches(torch, lambda: launch(*pick()), iters)
@@ -104,6 +127,11 @@ def ops_table(torch, B, workloads, iters=20):
             rec["GFLOPs_warm"] = round(flops / warm / 1e6, 1)
             rec["GFLOPs_cold"] = round(flops / cold / 1e6, 1)
             rec["frac_fp32_peak_warm"] = round(flops / warm / 1e6 / FP32_PEAK_GFLOPS, 4)
+        if graph:
+            rec["ms_in_graph"] = round(graph_ms(launch, first), 5)
+            rec["GBps_in_graph"] = round(nbytes / rec["ms_in_graph"] / 1e6, 1)
+            if flops:
+                rec["GFLOPs_in_graph"] = round(flops / rec["ms_in_graph"] / 1e6, 1)
         out[name] = rec
 
     g = lambda a: torch.from_numpy(a).cuda()
@@ -112,19 +140,19 @@ def ops_table(torch, B, workloads, iters=20):
     x1, t1 = g(x1), g(t1)
     mk = lambda: (x1.clone(), torch.empty(1, 1, 1048572, device="cuda"))
     nb = slide_bytes(1, 1048576, 5)
-    record("cfg1_slide_add_w5", lambda x, y: B.sws_slide1d(0, x, 5, 0.2, y=y), mk, nb)
-    record("cfg1_slide_max_w5", lambda x, y: B.sws_slide1d(1, x, 5, 1.0, y=y), mk, nb)
-    record("cfg1_corr_k5", lambda x, y: B.sws_conv1d(x, t1, y=y), mk, nb + 20, 2.0 * 5 * 1048572)
+    record("cfg1_slide_add_w5", lambda x, y: B.sws_slide1d(0, x, 5, 0.2, y=y), mk, nb, graph=True)
+    record("cfg1_slide_max_w5", lambda x, y: B.sws_slide1d(1, x, 5, 1.0, y=y), mk, nb, graph=True)
+    record("cfg1_corr_k5", lambda x, y: B.sws_conv1d(x, t1, y=y), mk, nb + 20, 2.0 * 5 * 1048572, graph=True)
     del x1
     # cfg2: [16,64,4096], pool w=3 and conv1d [64,64,3]
     x2, w2 = workloads.make(2)
     x2, w2 = g(x2), g(w2)
     mk = lambda: (x2.clone(), torch.empty(16, 64, 4094, device="cuda"))
     nb = slide_bytes(1024, 4096, 3)
-    record("cfg2_avgpool_w3", lambda x, y: B.sws_slide1d(0, x, 3, 1 / 3, y=y), mk, nb)
-    record("cfg2_maxpool_w3", lambda x, y: B.sws_slide1d(1, x, 3, 1.0, y=y), mk, nb)
+    record("cfg2_avgpool_w3", lambda x, y: B.sws_slide1d(0, x, 3, 1 / 3, y=y), mk, nb, graph=True)
+    record("cfg2_maxpool_w3", lambda x, y: B.sws_slide1d(1, x, 3, 1.0, y=y), mk, nb, graph=True)
     record("cfg2_conv1d_64x64x3", lambda x, y: B.sws_conv1d(x, w2, y=y), mk, nb + 4 * 64 * 64 * 3,
-           2.0 * 16 * 64 * 4094 * 64 * 3)
+           2.0 * 16 * 64 * 4094 * 64 * 3, graph=True)
     del x2
     # cfg3: [32,64,112,112] 3x3 pad 1, stride 1 and 2
     x3, _ = workloads.make(3)

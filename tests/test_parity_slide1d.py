@@ -155,3 +155,45 @@ def test_cfg2_pooling_full_size(B):
     x, _ = workloads.make(2)
     _check(B, "add", x.reshape(-1, 4096), 3, scale=1.0 / 3, what="cfg2 avg")
     _check(B, "max", x.reshape(-1, 4096), 3, what="cfg2 max")
+
+
+def test_graph_replay_matches_eager(B):
+    """The entry points only enqueue kernels on the caller's stream, so a launch-bound sequence can
+    be captured in a HIP graph.  Several replays, with eager work and synchronisation between them
+    and fresh inputs each time, must reproduce the eager results bit for bit."""
+    import torch
+    r = np.random.Generator(np.random.PCG64(2024))
+    x = to_gpu((r.random((1, 1, 100000), dtype=np.float32) * 2 - 1).astype(np.float32))
+    taps = to_gpu(r.standard_normal((1, 1, 5), dtype=np.float32))
+    ya, ym, yc = (torch.empty(1, 1, 99996, device="cuda") for _ in range(3))
+    yp = torch.empty(1, 1, 100000, device="cuda")
+
+    def launch_all():
+        B.sws_slide1d(0, x, 5, 0.2, y=ya)
+        B.sws_slide1d(1, x, 5, 1.0, y=ym)
+        B.sws_conv1d(x, taps, y=yc)
+        B.sws_slide1d_padded(1, x, 5, 2, 2, B.SWS_PAD_MIRROR, 1.0, y=yp)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        launch_all()                                           # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        launch_all()
+    for rep in range(4):
+        x.copy_(to_gpu((r.random((1, 1, 100000), dtype=np.float32) * 2 - 1).astype(np.float32)))   # eager work between replays
+        for t in (ya, ym, yc, yp):
+            t.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (ya, ym, yc, yp)]
+        launch_all()                                           # eager, same inputs
+        torch.cuda.synchronize()
+        for a, b in zip(got, (ya, ym, yc, yp)):
+            assert torch.equal(a, b), "replay %d differs from the eager result" % rep
+        ref, mag = oracle.slide1d(0, to_host(x).reshape(1, -1), 5, 0.2)
+        assert_within_tol(to_host(got[0]).reshape(1, -1), ref, mag, "graph replay %d" % rep)
