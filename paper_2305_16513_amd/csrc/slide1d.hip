@@ -167,7 +167,10 @@ template <> struct SegStep<SWS_OP_MIN> {
     }
 };
 
-template <int OP, int C, bool PADDED>
+// MODE 0: plain rows.  MODE 1: rows extended by a boundary rule.  MODE 2: one link of a chain of
+// windows (see launch_chain): rows `pitch` apart of which `len` elements are used, results
+// combined with what an earlier link left in y.
+template <int OP, int C, int MODE>
 __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__restrict__ x,
                                                               float *__restrict__ y, int len, int lo, int S,
                                                               float scale, int tiles_per_row, int tout,
@@ -177,9 +180,12 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
 {
     // The row the windows slide over is the physical row of `len` elements extended to `lv`
     // (pad_left in front, the rest behind) by the boundary rule pad_mode; lo = lv - S outputs.
-    // The unpadded instantiation sees constants, so the common path carries none of this.
+    // The plain instantiation sees constants, so the common path carries none of this.
+    constexpr bool PADDED = MODE == 1;
     const int pad_left = PADDED ? pad_left_arg : 0, pad_mode = PADDED ? pad_mode_arg : SWS_PAD_IDENTITY;
     const int lv = PADDED ? lv_arg : len;
+    const int pitch = MODE == 2 ? lv_arg : len;     // distance between rows of x
+    const bool chain_acc = MODE == 2 && (pad_mode_arg & 1);   // combine with the earlier links' result in y
     using O = Op<OP>;
     using G = SegStep<OP>;
     static_assert(C == 16, "the LDS layout assumes 16-element chunks");
@@ -245,7 +251,7 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
     const int pre_pos0 = lds_pos(4 * (lane + s4)), pre_pos1 = lds_pos(4 * (lane + s4 + 1));
 
     for (; gt < gt_end; gt += kWavesPerWg) {
-        const float *xr = x + r * (int64_t)len;
+        const float *xr = x + r * (int64_t)pitch;
         // With aligned tiles the origin is pulled back so that (r*lo + t0) is a multiple of 16
         // floats: every 1 KB strip store then starts on a 64-byte line.  The first tile of a row
         // may start before the row (t0 < 0); those outputs are not stored.
@@ -337,7 +343,22 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
             }
             v4f o;
             o.x = O::f(s4v.x, pn.x); o.y = O::f(s4v.y, pn.y); o.z = O::f(s4v.z, pn.z); o.w = O::f(s4v.w, pn.w);
-            if (OP == SWS_OP_ADD) o *= scale;
+            if (MODE != 2) {
+                if (OP == SWS_OP_ADD) o *= scale;
+            } else {
+                if (chain_acc) {                     // earlier links cover older elements: they go on the left
+                    if (q >= qlo && q + 4 <= lim) {
+                        const v4f old = *(const v4f_u *)(yt + q);
+                        o.x = O::f(old.x, o.x); o.y = O::f(old.y, o.y); o.z = O::f(old.z, o.z); o.w = O::f(old.w, o.w);
+                    } else {
+                        if (q + 0 >= qlo && q + 0 < lim) o.x = O::f(yt[q + 0], o.x);
+                        if (q + 1 >= qlo && q + 1 < lim) o.y = O::f(yt[q + 1], o.y);
+                        if (q + 2 >= qlo && q + 2 < lim) o.z = O::f(yt[q + 2], o.z);
+                        if (q + 3 >= qlo && q + 3 < lim) o.w = O::f(yt[q + 3], o.w);
+                    }
+                }
+                if (OP == SWS_OP_ADD) o *= scale;    // 1 in every link but the last
+            }
             if (q >= qlo && q + 4 <= lim) {
                 if (flags & 2) __builtin_nontemporal_store(o, (v4f_u *)(yt + q));
                 else *(v4f_u *)(yt + q) = o;
@@ -380,7 +401,7 @@ hipError_t launch_direct(const float *x, float *y, int64_t rows, int len, int lo
 // 8 = force it off.
 template <int OP>
 hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, int w, float scale,
-                       int pad_left, int pad_mode, int lv, hipStream_t s)
+                       int pad_left, int pad_mode, int lv, hipStream_t s, int chain = 0, int pitch = 0)
 {
     constexpr int C = 16, N = kWave * C;
     const int S = w - 1;
@@ -413,17 +434,49 @@ hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, 
     const int64_t n_units = (n_tiles + g - 1) / g;
     const int64_t grid = remap ? xcd_grid(n_units) : n_units;
     if (grid > 2147483647LL) return hipErrorInvalidValue;
-    if (lv != len)
-        hipLaunchKernelGGL((slide_scan_kernel<OP, C, true>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
+    if (chain) {                                      // chain bits: 1 = combine with y, 2 = last link
+        if (!(chain & 2)) flags &= ~2;                // y is read again by the next link: plain stores
+        hipLaunchKernelGGL((slide_scan_kernel<OP, C, 2>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
+                           S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, 0, chain & 1, pitch);
+    } else if (lv != len) {
+        hipLaunchKernelGGL((slide_scan_kernel<OP, C, 1>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
                            S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, pad_left, pad_mode, lv);
-    else
-        hipLaunchKernelGGL((slide_scan_kernel<OP, C, false>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
+    } else {
+        hipLaunchKernelGGL((slide_scan_kernel<OP, C, 0>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
                            S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, 0, 0, len);
+    }
     return hipGetLastError();
+}
+
+// Windows longer than one tile can hold: w = w_0 + w_1 + ... with every w_j within the scan
+// kernel's reach, and  y[i] = Y_0[i] (+) Y_1[i + w_0] (+) Y_2[i + w_0 + w_1] ...  where Y_j is the
+// sliding sum of window w_j (associativity; the links go oldest first, so operand order holds).
+// Link j runs the scan kernel on the rows shifted by the earlier links' widths and combines its
+// result with what is already in y.  Each link after the first re-reads y, so a window of P links
+// moves 3P - 1 arrays instead of 2 — the work stays independent of w, where direct evaluation
+// does w operations per output.
+template <int OP>
+hipError_t launch_chain(const float *x, float *y, int64_t rows, int len, int lo, int w, float scale, hipStream_t s)
+{
+    int reach = 768;                                 // longest link (a tile keeps >= 25 % of its elements as outputs)
+    if ((g_opt.slide_chunk >> 8) > 1) reach = g_opt.slide_chunk >> 8;      // A/B: link length
+    int links = (w + reach - 1) / reach;
+    if (links < 2) links = 2;
+    int done = 0;
+    for (int j = 0; j < links; ++j) {
+        const int wj = (w - done) / (links - j);    // near-equal widths, each >= 2
+        const bool last = j == links - 1;
+        const hipError_t e = launch_scan<OP>(x + done, y, rows, lo + wj - 1, lo, wj, last ? scale : 1.0f, 0, 0,
+                                             lo + wj - 1, s, 4 | (j > 0 ? 1 : 0) | (last ? 2 : 0), len);
+        if (e != hipSuccess) return e;
+        done += wj;
+    }
+    return hipSuccess;
 }
 
 constexpr int kDirectMaxW = 9;
 constexpr int kScanMaxW = kWave * 16 - 64 + 1;      // leaves at least 64 outputs per wave tile
+constexpr int kChainMinW = 850;                     // longer windows run as a chain of shorter ones
 
 }  // namespace
 
@@ -437,7 +490,21 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
     if (variant == 2 && w > kDirectMaxW) variant = 0;
     if (variant == 3 && (w < 2 || w > kScanMaxW)) variant = 0;
     if (variant == 4) return launch_slide1d_generic(op, x, y, rows, len64, w, scale, s);   // generic-operator kernel (A/B)
-    if (variant == 0) variant = (w == 1) ? (padded ? 1 : 2) : (w <= kScanMaxW ? 3 : 1);
+    // Measured on 16384-long rows: beyond w = 850 two links of half the width beat one pass whose
+    // tiles are mostly halo.
+    if (variant == 0) {
+        if (w == 1) variant = padded ? 1 : 2;
+        else if (padded) variant = w <= kScanMaxW ? 3 : 1;
+        else variant = w <= kChainMinW ? 3 : 5;
+    }
+    if (variant == 5) {                              // longer than a tile: a chain of windows
+        if (padded || w < 4) variant = 1;
+        else switch (op) {
+            case SWS_OP_ADD: return launch_chain<SWS_OP_ADD>(x, y, rows, len, lo, w, scale, s);
+            case SWS_OP_MAX: return launch_chain<SWS_OP_MAX>(x, y, rows, len, lo, w, scale, s);
+            default: return launch_chain<SWS_OP_MIN>(x, y, rows, len, lo, w, scale, s);
+        }
+    }
     if (variant == 1) return launch_slide1d_naive(op, x, y, rows, len64, w, pad_left, pad_right, pad_mode, scale, s);
     if (variant == 2) {
         switch (op) {

@@ -197,3 +197,35 @@ def test_graph_replay_matches_eager(B):
             assert torch.equal(a, b), "replay %d differs from the eager result" % rep
         ref, mag = oracle.slide1d(0, to_host(x).reshape(1, -1), 5, 0.2)
         assert_within_tol(to_host(got[0]).reshape(1, -1), ref, mag, "graph replay %d" % rep)
+
+
+@pytest.mark.parametrize("op", [0, 1, 2])
+@pytest.mark.parametrize("w,length", [(851, 2000), (962, 2000), (1500, 1500), (1537, 7000), (2048, 20000), (5000, 20011),
+                                      (16384, 16385)])
+def test_windows_longer_than_a_tile_run_as_a_chain(B, op, w, length):
+    """w > 961: the window is split into links within the scan kernel's reach, each link combined
+    with the earlier ones in y (operand order kept: add within tolerance, max / min bit-exact)."""
+    r = np.random.Generator(np.random.PCG64(op * 100000 + w))
+    x = (r.random((3, length), dtype=np.float32) * 2 - 1).astype(np.float32)
+    y = to_host(B.sws_slide1d(op, to_gpu(x), w, 1.0 / w))
+    ref, mag = oracle.slide1d(op, x, w, 1.0 / w)
+    if op == 0:
+        assert_within_tol(y, ref, mag, "chain add w=%d" % w)
+    else:
+        assert_bit_exact(y, ref, "chain op %d w=%d" % (op, w))
+    B.sws_set_option("slide_variant", 1)                        # and the direct-evaluation kernel agrees
+    try:
+        y1 = to_host(B.sws_slide1d(op, to_gpu(x), w, 1.0 / w))
+    finally:
+        B.sws_set_option("slide_variant", 0)
+    if op == 0:
+        assert_within_tol(y1, ref, mag, "direct add w=%d" % w)
+    else:
+        assert_bit_exact(y1, ref, "direct op %d w=%d" % (op, w))
+
+
+def test_chain_on_integer_valued_input_is_exact(B):
+    x = workloads.integer_valued((2, 9000), -8, 8, seed=12)
+    y = to_host(B.sws_slide1d(0, to_gpu(x), 3001, 1.0))
+    ref, _ = oracle.slide1d(0, x, 3001, 1.0)
+    assert np.array_equal(y.astype(np.float64), ref)
