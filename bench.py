@@ -219,6 +219,15 @@ def sweeps_table(torch, B, workloads, iters=20):
                                                "frac_valu_peak": round(fl / ms / 1e9 / 78.6, 4)}
     del x7, y
     torch.cuda.empty_cache()
+    # the dense form of the same scenario: 16 -> 16 channels, batch 64, chunks of taps on the matrix cores
+    xd = g(workloads.make(7, x_shape=(64, 16, 100000 + (k - 1) * d), wgt_shape=(16, 16, k))[0])
+    wd = g(workloads.make(7, x_shape=(1,), wgt_shape=(16, 16, k))[1])
+    yd = torch.empty(64, 16, 100000, device="cuda")
+    ms = time_launches(torch, lambda: B.sws_conv1d(xd, wd, 1, 0, d, 1, y=yd), iters)
+    out["dilated_batched"]["dense_16x16_k51_d8_q100000_b64"] = {
+        "ms": round(ms, 4), "TFLOPs": round(2.0 * 64 * 16 * 100000 * 16 * k / ms / 1e9, 2)}
+    del xd, yd
+    torch.cuda.empty_cache()
     # sliding window sum under the pair operator (Section 2.4, Eq. 8): 16 algorithmic bytes per output
     u, v = workloads.make_pairs()
     u, v = g(u), g(v)

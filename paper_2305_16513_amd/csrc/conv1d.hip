@@ -400,7 +400,7 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
 {
     int variant = g_opt.conv1d_variant;
     const bool thin_ok = (Cin / groups == 1) && stride == 1 && dilation == 1 && k <= kThinMaxK;
-    const bool dense_ok = groups == 1 && Cin >= 2 && dilation == 1;
+    const bool dense_ok = groups == 1 && Cin >= 2;
     DilPlan dpl;
     const bool thin_dil_ok = (Cin / groups == 1) && stride == 1 && dilation > 1 && k <= kThinMaxK && L >= 4 &&
                              plan_dilated(dilation, 4 * ((k + 3) / 4), &dpl);
@@ -411,7 +411,7 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
     if (variant == 3) {
         // the dense contraction is the 2-D kernel on images of height 1
         bool taken = false;
-        const hipError_t e = launch_conv2d_mfma(x, wgt, y, B, Cin, 1, L, Cout, 1, Lo, 1, k, 1, stride, 0, pad, s, &taken);
+        const hipError_t e = launch_conv2d_mfma(x, wgt, y, B, Cin, 1, L, Cout, 1, Lo, 1, k, 1, stride, 0, pad, 1, dilation, s, &taken);
         if (taken) return e;
         variant = 1;
     }

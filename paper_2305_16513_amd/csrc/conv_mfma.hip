@@ -38,6 +38,9 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 struct ConvGeom {
     int Cin, H, W, Cout, Ho, Wo, kh, kw, ph, pw;
     int sh, sw;                                       // strides (the channel-fastest kernel only)
+    int dh, dw;                                       // tap spacing (ditto)
+    int wstride, wofs;                                // taps per (co, ci) pair in memory; first tap of this launch
+    int accum;                                        // add to what y already holds (a later chunk of taps)
     int mode_b;                                       // 0: flat tiles over rows, 1: column tiles of one row
     int NP;                                           // output positions per workgroup
     int Wt, NRows, CP;                                // staged row pitch, staged rows, channel pitch in LDS
@@ -343,7 +346,7 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
     const int w_co = (threadIdx.x >> 3) & (kCoTile - 1), w_ci = threadIdx.x & 7;
     const bool w_mine = threadIdx.x < kCoTile * 8;    // the first 512 threads move the weights
     const bool w_ok = w_mine && co0 + w_co < g.Cout;
-    const float *wsrc = wgt + (w_ok ? ((int64_t)(co0 + w_co) * g.Cin + w_ci) * KT : 0);
+    const float *wsrc = wgt + (w_ok ? ((int64_t)(co0 + w_co) * g.Cin + w_ci) * g.wstride + g.wofs : 0);
     float *wdst = Wl + w_co * XP + w_ci;
 
     float xreg[NB][XS], wreg[NB][KTMAX];
@@ -357,7 +360,7 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
             const int xb = (ci0 + nb * CIB) * plane;
 #pragma unroll
             for (int s = 0; s < XS; ++s) xreg[nb][s] = xn[xg[s] >= 0 ? xb + xg[s] : 0];
-            const float *w = wsrc + (w_ok ? (ci0 + nb * CIB) * KT : 0);
+            const float *w = wsrc + (w_ok ? (ci0 + nb * CIB) * g.wstride : 0);
 #pragma unroll
             for (int t = 0; t < KTMAX; ++t) wreg[nb][t] = w[t < KT ? t : 0];
         }
@@ -386,7 +389,7 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
             if (KTT > 0) {
 #pragma unroll
                 for (int tap = 0; tap < (KTT > 0 ? KTT : 1); ++tap) {
-                    const int shift = (tap / 3) * g.Wt + (tap % 3);      // KTT > 0 is only used with kw == 3
+                    const int shift = (tap / 3) * g.dh * g.Wt + (tap % 3) * g.dw;    // KTT > 0 is only used with kw == 3
                     const v4f a4 = *(const v4f *)(Wb + tap * kCoTile * XP + a_lane);
                     const v4f b4 = *(const v4f *)(Xb + shift * XP + b_lane);
                     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, b4.x, acc, 0, 0, 0);
@@ -397,7 +400,7 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
             } else {
                 int ta = 0, tb = 0;
                 for (int tap = 0; tap < KT; ++tap) {
-                    const int shift = ta * g.Wt + tb;
+                    const int shift = ta * g.dh * g.Wt + tb * g.dw;
                     const v4f a4 = *(const v4f *)(Wb + tap * kCoTile * XP + a_lane);
                     const v4f b4 = *(const v4f *)(Xb + shift * XP + b_lane);
                     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, b4.x, acc, 0, 0, 0);
@@ -415,25 +418,29 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int co = co0 + wm * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-        if (co < g.Cout) yn[((int64_t)co * g.Ho + oh) * g.Wo + ow] = acc[v];
+        if (co < g.Cout) {
+            float *dst = yn + ((int64_t)co * g.Ho + oh) * g.Wo + ow;
+            *dst = g.accum ? *dst + acc[v] : acc[v];
+        }
     }
 }
 
 bool plan(ConvGeom &g, int NP, int CIB, int xslots_total, int64_t N, int64_t *n_units, size_t *lds_bytes)
 {
     g.NP = NP;
-    if ((g.Wo - 1) * g.sw + g.kw <= 192) {            // mode A: flat tiles, full-width rows
+    const int span_h = (g.kh - 1) * g.dh + 1, span_w = (g.kw - 1) * g.dw + 1;     // reach of the taps
+    if ((g.Wo - 1) * g.sw + span_w <= 192) {          // mode A: flat tiles, full-width rows
         g.mode_b = 0;
-        g.Wt = (g.Wo - 1) * g.sw + g.kw;
+        g.Wt = (g.Wo - 1) * g.sw + span_w;
         // output rows a tile can touch (tiles of whole rows always start on a row)
         const int rows = (g.NP % g.Wo == 0) ? g.NP / g.Wo : (g.NP + g.Wo - 2) / g.Wo + 1;
-        g.NRows = ((rows < g.Ho ? rows : g.Ho) - 1) * g.sh + g.kh;
+        g.NRows = ((rows < g.Ho ? rows : g.Ho) - 1) * g.sh + span_h;
         g.tiles_c = 1;
         g.tiles_per_img = (g.Ho * g.Wo + g.NP - 1) / g.NP;
     } else {                                          // mode B: column tiles of single rows
         g.mode_b = 1;
-        g.Wt = (g.NP - 1) * g.sw + g.kw;
-        g.NRows = g.kh;
+        g.Wt = (g.NP - 1) * g.sw + span_w;
+        g.NRows = span_h;
         g.tiles_c = (g.Wo + g.NP - 1) / g.NP;
         g.tiles_per_img = g.Ho * g.tiles_c;
     }
@@ -463,86 +470,150 @@ hipError_t launch(const float *x, const float *wgt, float *y, const ConvGeom &g,
 
 }  // namespace
 
-// Undilated, groups = 1 convolution on the matrix cores (strides in the channel-fastest kernel).  *taken = false means the
-// shape is outside what this kernel covers and nothing was launched.
-hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
-                              int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh,
-                              int32_t sw, int32_t ph, int32_t pw, hipStream_t s, bool *taken)
-{
-    *taken = false;
-    const bool strided = sh != 1 || sw != 1;
-    const int KT = kh * kw;
-    // channel blocks of 16 (or 4 for big kernels / odd channel counts) must divide Cin
-    const int CIB = (KT <= 9 && Cin % 16 == 0) ? 16 : ((KT <= 36 && Cin % 4 == 0) ? 4 : 0);
-    if (CIB == 0 || Ho * Wo > 2147483647LL / 2 || Cout * Cin * KT > 2147483647LL / 2) return hipSuccess;
+namespace {
+
+// One launch of the channel-fastest kernel, fully decided on the host before anything runs.
+struct C8Launch {
     ConvGeom g;
-    g.Cin = (int)Cin; g.H = (int)H; g.W = (int)W; g.Cout = (int)Cout; g.Ho = (int)Ho; g.Wo = (int)Wo;
-    g.kh = kh; g.kw = kw; g.ph = ph; g.pw = pw; g.sh = sh; g.sw = sw;
+    SegPlan sp;
+    dim3 grid;
+    size_t lds;
+    int waves, ktt, nb, seg;
+};
+
+// Decides tile width and template instance for the geometry in L->g (kh * kw <= 9, Cin % 8 == 0).
+bool c8_prepare(C8Launch *L, int64_t N)
+{
+    ConvGeom &g = L->g;
+    const int KT = g.kh * g.kw;
     int64_t units = 0;
     size_t lds = 0;
-    // preferred: channel-fastest tiles with 128-bit operand reads (kh*kw <= 9, Cin % 8 == 0)
-    if (KT <= 9 && Cin % 8 == 0 && g_opt.conv2d_variant != 3 && g_opt.conv2d_variant != 4) {
-        // Tile width: 8 to 14 wavefronts (128 to 224 positions).  Two workgroups share a compute unit,
-        // so the launch takes ceil(workgroups / 512) rounds of `waves` accumulator blocks each.
-        int best_w = 0;
-        int64_t best_cost = 0;
-        for (int wv = 8; wv <= 14; wv += 2) {
-            if (g_opt.conv2d_variant >= 8 && g_opt.conv2d_variant != wv) continue;     // A/B: force a width
-            ConvGeom t = g;
-            if (!plan(t, 16 * wv, 16, 1 << 30, N, &units, &lds)) continue;
-            const int xfl = (t.NRows * t.Wt * 12 + 3) / 4 * 4;
-            // staging plan: up to 64 row segments per channel block, 128 with 8 wavefronts
-            if (8 * t.NRows * t.CH > (wv == 8 ? 128 : 64) || t.NRows >= 256 ||
-                4 * ((size_t)xfl + (size_t)KT * kCoTile * 12) > 64 * 1024)
-                continue;
-            const int64_t cost = ((units + 511) / 512) * wv;
-            if (best_w == 0 || cost < best_cost) { best_w = wv; best_cost = cost; }
-        }
-        if (best_w != 0 && N <= 65535 && (Cout + kCoTile - 1) / kCoTile <= 65535) {
-            plan(g, 16 * best_w, 16, 1 << 30, N, &units, &lds);
-            const int xfloats = (g.NRows * g.Wt * 12 + 3) / 4 * 4;
-            const size_t lds1 = 4 * ((size_t)xfloats + (size_t)KT * kCoTile * 12);
-            // few taps: four channel blocks per barrier pair, if they fit
-            const bool nb4 = KT == 3 && kw == 3 && Cin % 32 == 0 && 8 * g.NRows * g.CH <= 32 && 4 * lds1 <= 64 * 1024 &&
-                             g_opt.conv2d_variant != 5;
-            const size_t lds8 = (nb4 ? 4 : 1) * lds1;
-            g.CP = xfloats;
-            const bool seg128 = 8 * g.NRows * g.CH > 64;      // only reached with 8 wavefronts
-            SegPlan sp;
-            for (int i = 0; i < 128; ++i) {
-                const int ci = i / (g.NRows * g.CH), r2 = i % (g.NRows * g.CH);
-                sp.e[i] = (unsigned)(ci < 8 ? ci : 0) | (unsigned)(r2 / g.CH) << 8 | (unsigned)(r2 % g.CH) << 16;
-            }
-            const dim3 grid((unsigned)g.tiles_per_img, (unsigned)g.co_blocks, (unsigned)N);
-            *taken = true;
+    // Tile width: 8 to 14 wavefronts (128 to 224 positions).  Two workgroups share a compute unit,
+    // so the launch takes ceil(workgroups / 512) rounds of `waves` accumulator blocks each.
+    int best_w = 0;
+    int64_t best_cost = 0;
+    for (int wv = 8; wv <= 14; wv += 2) {
+        if (g_opt.conv2d_variant >= 8 && g_opt.conv2d_variant != wv) continue;     // A/B: force a width
+        ConvGeom t = g;
+        if (!plan(t, 16 * wv, 16, 1 << 30, N, &units, &lds)) continue;
+        const int xfl = (t.NRows * t.Wt * 12 + 3) / 4 * 4;
+        // staging plan: up to 64 row segments per channel block, 128 with 8 wavefronts
+        if (8 * t.NRows * t.CH > (wv == 8 ? 128 : 64) || t.NRows >= 256 ||
+            4 * ((size_t)xfl + (size_t)KT * kCoTile * 12) > 64 * 1024)
+            continue;
+        const int64_t cost = ((units + 511) / 512) * wv;
+        if (best_w == 0 || cost < best_cost) { best_w = wv; best_cost = cost; }
+    }
+    if (best_w == 0 || N > 65535 || (g.Cout + kCoTile - 1) / kCoTile > 65535) return false;
+    plan(g, 16 * best_w, 16, 1 << 30, N, &units, &lds);
+    const int xfloats = (g.NRows * g.Wt * 12 + 3) / 4 * 4;
+    const size_t lds1 = 4 * ((size_t)xfloats + (size_t)KT * kCoTile * 12);
+    // few taps: four channel blocks per barrier pair, if they fit
+    const bool nb4 = KT == 3 && g.kw == 3 && g.Cin % 32 == 0 && 8 * g.NRows * g.CH <= 32 && 4 * lds1 <= 64 * 1024 &&
+                     g_opt.conv2d_variant != 5;
+    const bool seg128 = 8 * g.NRows * g.CH > 64;          // only reached with 8 wavefronts (strided: tall tiles)
+    g.CP = xfloats;
+    for (int i = 0; i < 128; ++i) {
+        const int ci = i / (g.NRows * g.CH), r2 = i % (g.NRows * g.CH);
+        L->sp.e[i] = (unsigned)(ci < 8 ? ci : 0) | (unsigned)(r2 / g.CH) << 8 | (unsigned)(r2 % g.CH) << 16;
+    }
+    L->grid = dim3((unsigned)g.tiles_per_img, (unsigned)g.co_blocks, (unsigned)N);
+    L->lds = (nb4 ? 4 : 1) * lds1;
+    L->waves = seg128 ? 8 : best_w;
+    L->ktt = (KT == 9 && g.kw == 3) ? 9 : ((KT == 3 && g.kw == 3) ? 3 : 0);
+    L->nb = (nb4 && !seg128) ? 4 : 1;
+    L->seg = seg128 ? 128 : (L->nb == 4 ? 32 : 64);
+    return true;
+}
+
+hipError_t c8_launch(const C8Launch &L, const float *x, const float *wgt, float *y, hipStream_t s)
+{
 #define SWS_C8(KTT, WV, NB, SEG)                                                                                \
-    hipLaunchKernelGGL((conv2d_mfma_c8_kernel<KTT, WV, NB, SEG>), grid, dim3(WV * 64), lds8, s, x, wgt, y, g, sp)
+    hipLaunchKernelGGL((conv2d_mfma_c8_kernel<KTT, WV, NB, SEG>), L.grid, dim3(WV * 64), L.lds, s, x, wgt, y, L.g, L.sp)
 #define SWS_C8_W(KTT, NB, SEG)                                                                                  \
-    switch (best_w) {                                                                                           \
+    switch (L.waves) {                                                                                          \
     case 8: SWS_C8(KTT, 8, NB, SEG); break;                                                                     \
     case 10: SWS_C8(KTT, 10, NB, SEG); break;                                                                   \
     case 12: SWS_C8(KTT, 12, NB, SEG); break;                                                                   \
     default: SWS_C8(KTT, 14, NB, SEG); break;                                                                   \
     }
-            if (seg128) {                                 // tall input tiles (strided convolution)
-                if (KT == 9 && kw == 3) SWS_C8(9, 8, 1, 128);
-                else if (KT == 3 && kw == 3) SWS_C8(3, 8, 1, 128);
-                else SWS_C8(0, 8, 1, 128);
-            } else if (KT == 9 && kw == 3) {
-                SWS_C8_W(9, 1, 64)
-            } else if (nb4) {
-                SWS_C8_W(3, 4, 32)
-            } else if (KT == 3 && kw == 3) {
-                SWS_C8_W(3, 1, 64)
-            } else {
-                SWS_C8_W(0, 1, 64)
-            }
+    if (L.seg == 128) {
+        if (L.ktt == 9) SWS_C8(9, 8, 1, 128);
+        else if (L.ktt == 3) SWS_C8(3, 8, 1, 128);
+        else SWS_C8(0, 8, 1, 128);
+    } else if (L.ktt == 9) {
+        SWS_C8_W(9, 1, 64)
+    } else if (L.nb == 4) {
+        SWS_C8_W(3, 4, 32)
+    } else if (L.ktt == 3) {
+        SWS_C8_W(3, 1, 64)
+    } else {
+        SWS_C8_W(0, 1, 64)
+    }
 #undef SWS_C8_W
 #undef SWS_C8
-            return hipGetLastError();
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// groups = 1 convolution on the matrix cores.  The channel-fastest kernel takes strides and tap
+// spacing, and kernels of more than 9 taps run as a chain of launches over chunks of taps (whole
+// kernel rows, or runs of taps of a one-row kernel), each adding to what the earlier ones left in
+// y: the sliding sum over taps, cut into pieces.  *taken = false means the shape is outside what
+// these kernels cover and nothing was launched.
+hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
+                              int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh,
+                              int32_t sw, int32_t ph, int32_t pw, int32_t dh, int32_t dw, hipStream_t s, bool *taken)
+{
+    *taken = false;
+    const bool plain = sh == 1 && sw == 1 && dh == 1 && dw == 1;
+    const int KT = kh * kw;
+    if (Ho * Wo > 2147483647LL / 2 || Cout * Cin * KT > 2147483647LL / 2) return hipSuccess;
+    ConvGeom g;
+    g.Cin = (int)Cin; g.H = (int)H; g.W = (int)W; g.Cout = (int)Cout; g.Ho = (int)Ho; g.Wo = (int)Wo;
+    g.kh = kh; g.kw = kw; g.ph = ph; g.pw = pw; g.sh = sh; g.sw = sw; g.dh = dh; g.dw = dw;
+    g.wstride = KT; g.wofs = 0; g.accum = 0;
+    // Up to 36 adjacent taps at stride 1 the scalar-read kernel does the whole kernel in one pass,
+    // which beats a chain of five or more launches (5 x 5 on [32,64,56,56]: 0.27 ms against 0.41 ms).
+    const bool one_pass = plain && KT > 9 && KT <= 36 && Cin % 4 == 0 && g_opt.conv2d_variant != 6;
+    // preferred: channel-fastest tiles with 128-bit operand reads (Cin % 8 == 0)
+    if (!one_pass && Cin % 8 == 0 && g_opt.conv2d_variant != 3 && g_opt.conv2d_variant != 4 &&
+        (KT <= 9 || kh == 1 || kw <= 9)) {
+        // chunks of at most 9 taps: runs of a one-row kernel, or whole rows of a taller one
+        const bool along_w = KT > 9 && kh == 1;
+        const int per = KT <= 9 ? (along_w ? kw : kh) : (along_w ? 9 : 9 / kw);      // taps / rows per chunk
+        const int total = along_w ? kw : kh;
+        const int n_chunks = KT <= 9 ? 1 : (total + per - 1) / per;
+        if (n_chunks <= 64) {
+            C8Launch L[64];
+            bool ok = true;
+            for (int c = 0; c < n_chunks && ok; ++c) {
+                const int first = c * per, cnt = (total - first < per) ? total - first : per;
+                L[c].g = g;
+                if (KT > 9) {
+                    if (along_w) { L[c].g.kw = cnt; L[c].g.pw = pw - first * dw; L[c].g.wofs = first; }
+                    else { L[c].g.kh = cnt; L[c].g.ph = ph - first * dh; L[c].g.wofs = first * kw; }
+                }
+                L[c].g.accum = c > 0;
+                ok = c8_prepare(&L[c], N);
+            }
+            if (ok) {
+                *taken = true;
+                for (int c = 0; c < n_chunks; ++c) {
+                    const hipError_t e = c8_launch(L[c], x, wgt, y, s);
+                    if (e != hipSuccess) return e;
+                }
+                return hipSuccess;
+            }
         }
     }
-    if (strided) return hipSuccess;                   // the scalar-read kernels below are stride-1 only
+    if (!plain) return hipSuccess;                    // the scalar-read kernels below: stride 1, taps adjacent
+    // channel blocks of 16 (or 4 for big kernels / odd channel counts) must divide Cin
+    const int CIB = (KT <= 9 && Cin % 16 == 0) ? 16 : ((KT <= 36 && Cin % 4 == 0) ? 4 : 0);
+    if (CIB == 0) return hipSuccess;
+    int64_t units = 0;
+    size_t lds = 0;
     if (!plan(g, 128, CIB, CIB == 16 ? 128 : 64, N, &units, &lds)) return hipSuccess;
     *taken = true;
     if (g_opt.conv2d_variant == 3) {                  // 4 wavefronts, two channel blocks each (A/B)

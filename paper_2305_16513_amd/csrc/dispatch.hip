@@ -9,7 +9,7 @@ hipError_t launch_conv2d(const float *x, const float *wgt, float *y, int64_t N, 
 {
     if (g_opt.conv2d_variant != 1) {
         bool taken = false;
-        const hipError_t e = launch_conv2d_mfma(x, wgt, y, N, Cin, H, W, Cout, Ho, Wo, kh, kw, sh, sw, ph, pw, s, &taken);
+        const hipError_t e = launch_conv2d_mfma(x, wgt, y, N, Cin, H, W, Cout, Ho, Wo, kh, kw, sh, sw, ph, pw, 1, 1, s, &taken);
         if (taken) return e;
     }
     return launch_conv2d_naive(x, wgt, y, N, Cin, H, W, Cout, Ho, Wo, kh, kw, sh, sw, ph, pw, s);

@@ -144,6 +144,9 @@ def test_conv2d(B, cin, cout, kh, kw, h, w_, geom):
     (24, 33, 2, 2, 17, 40, 0, 1),      # even tap count, Cout not a multiple of 32
     (64, 64, 6, 6, 20, 20, 2, 2),      # 36 taps
     (64, 64, 7, 7, 20, 20, 3, 3),      # 49 taps: beyond the matrix kernels, direct evaluation
+    (32, 32, 5, 5, 28, 28, 2, 2),      # 25 taps, Cin % 8 == 0: five chunks of one kernel row each
+    (8, 16, 4, 2, 19, 23, 1, 0),       # 8 taps in one launch; (16, 16, 4, 4): rows in chunks of two
+    (16, 16, 4, 4, 19, 23, 1, 2),
     (64, 48, 1, 3, 11, 40, 0, 1),      # 1 x 3 taps, Cin % 32 == 0: four channel blocks per barrier pair
     (32, 64, 1, 3, 3, 500, 0, 1),      # the same on wide rows (column tiles)
 ])
@@ -169,12 +172,41 @@ def test_conv2d_strided(B, cin, cout, kh, kw, h, w_, sh, sw, ph, pw):
     _c2(B, x, w, sh, sw, ph, pw, what=str((cin, cout, kh, kw, h, w_, sh, sw, ph, pw)))
 
 
+@pytest.mark.parametrize("cin,cout,k,dilation,pad,stride,length", [
+    (16, 16, 51, 8, 200, 1, 3000),     # a very long dilated kernel on few channels: six chunks of taps
+    (16, 16, 51, 8, 0, 1, 1000),
+    (32, 40, 11, 1, 5, 1, 1500),       # 11 taps: two chunks
+    (8, 8, 10, 3, 13, 2, 700),         # chunks + dilation + stride
+    (64, 64, 3, 4, 4, 1, 2000),        # three dilated taps in one launch
+    (24, 16, 31, 2, 30, 1, 900),
+])
+def test_conv1d_dense_dilated_and_long_kernels(B, cin, cout, k, dilation, pad, stride, length):
+    r = _rng(cin + cout + k * 3 + dilation)
+    x = r.standard_normal((2, cin, length), dtype=np.float32)
+    w = (r.standard_normal((cout, cin, k), dtype=np.float32) * np.sqrt(2.0 / (cin * k))).astype(np.float32)
+    _c1(B, x, w, stride=stride, pad=pad, dilation=dilation, what="dense k=%d d=%d" % (k, dilation))
+
+
 @pytest.mark.parametrize("stride,k,pad", [(2, 3, 1), (3, 5, 2), (2, 1, 0), (4, 9, 4)])
 def test_conv1d_dense_strided(B, stride, k, pad):
     r = _rng(stride * 10 + k)
     x = r.standard_normal((3, 32, 1500), dtype=np.float32)
     w = (r.standard_normal((48, 32, k), dtype=np.float32) * np.sqrt(2.0 / (32 * k))).astype(np.float32)
     _c1(B, x, w, stride=stride, pad=pad, what="dense stride=%d k=%d" % (stride, k))
+
+
+@pytest.mark.parametrize("cin,cout,kh,kw,ph,pw", [(32, 32, 5, 5, 2, 2), (16, 16, 4, 4, 1, 2), (8, 8, 6, 3, 0, 1), (64, 64, 7, 7, 3, 3)])
+def test_conv2d_chunks_of_kernel_rows(B, cin, cout, kh, kw, ph, pw):
+    """Kernels of more than 9 taps as a chain of launches over whole kernel rows, each adding to y
+    (forced here also where the one-pass kernel would be chosen)."""
+    r = _rng(cin + kh * 13 + kw)
+    x = r.standard_normal((2, cin, 30, 41), dtype=np.float32)
+    w = (r.standard_normal((cout, cin, kh, kw), dtype=np.float32) * np.sqrt(2.0 / (cin * kh * kw))).astype(np.float32)
+    B.sws_set_option("conv2d_variant", 6)
+    try:
+        _c2(B, x, w, 1, 1, ph, pw, what="row chunks %dx%d" % (kh, kw))
+    finally:
+        B.sws_set_option("conv2d_variant", 0)
 
 
 @pytest.mark.parametrize("variant", [1, 3, 8, 10, 12, 14])
