@@ -229,3 +229,36 @@ def test_chain_on_integer_valued_input_is_exact(B):
     y = to_host(B.sws_slide1d(0, to_gpu(x), 3001, 1.0))
     ref, _ = oracle.slide1d(0, x, 3001, 1.0)
     assert np.array_equal(y.astype(np.float64), ref)
+
+
+def test_longest_supported_row(B):
+    """One row of the largest length the ABI accepts (2^31 - 1 - 65536 elements, 8.6 GB): 32-bit
+    tile arithmetic at its limit.  The oracle checks stretches at the start, the end and seeded
+    places in between; one element more is an argument error (checked before anything is touched)."""
+    import torch
+    length = 2 ** 31 - 1 - 65536
+    free, _ = torch.cuda.mem_get_info()
+    if free < 4 * length * 2.2:
+        pytest.skip("not enough device memory for the longest row")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(31)
+    x = torch.rand(1, length, device="cuda", generator=g) * 2 - 1
+    r = np.random.Generator(np.random.PCG64(31))
+    n = 3000
+    for op, w in ((0, 16), (1, 255), (0, 900)):
+        lo = length - w + 1
+        y = B.sws_slide1d(op, x, w, 1.0)
+        assert y.shape == (1, lo)
+        starts = [0, lo - n] + [int(v) for v in r.integers(0, lo - n, size=5)] + [2 ** 30 - 1500, 2 ** 31 - 70000 - n]
+        for s0 in starts:
+            s0 = min(max(s0, 0), lo - n)
+            ref, mag = oracle.slide1d(op, to_host(x[:, s0:s0 + n + w - 1]), w, 1.0)
+            got = to_host(y[:, s0:s0 + n])
+            if op == 0:
+                assert_within_tol(got, ref, mag, "longest row add w=%d at %d" % (w, s0))
+            else:
+                assert_bit_exact(got, ref, "longest row max w=%d at %d" % (w, s0))
+        del y
+    del x
+    torch.cuda.empty_cache()
+    assert B.lib().sws_slide1d(0, 16, 16, 1, length + 1, 16, 1.0, None) == B.SWS_ERR_INVALID_ARG
