@@ -618,3 +618,48 @@ def test_padded_without_padding_is_the_plain_sliding_sum_and_periodic_wraps():
         oracle.slide1d_padded(OP_ADD, x, 3, 50, 0, oracle.PAD_MIRROR)           # mirror reaches past the row
     with pytest.raises(ValueError):
         oracle.slide1d_padded(OP_ADD, x, 3, 0, 51, oracle.PAD_PERIODIC)
+
+
+# ----------------------------------------------------------------------------- P11
+# Adjoint identities: <A x, g> = <x, A^T g> ties the plain, padded and convolution functions
+# together (the backward pass of pooling / convolution is again a sliding sum).
+@pytest.mark.parametrize("w", [1, 2, 5, 16])
+def test_adjoint_of_sliding_add_is_identity_padded_sliding_add(w):
+    r = _rng(110 + w)
+    x = r.standard_normal((2, 61), dtype=np.float32)
+    y, _ = oracle.slide1d(OP_ADD, x, w)
+    g = r.standard_normal(y.shape).astype(np.float32)
+    gx, _ = oracle.slide1d_padded(OP_ADD, g, w, w - 1, w - 1, oracle.PAD_IDENTITY)      # A^T g
+    assert gx.shape == x.shape
+    assert abs(float((y * g).sum()) - float((x.astype(np.float64) * gx).sum())) < 1e-10
+
+
+@pytest.mark.parametrize("k,dilation,pad", [(1, 1, 0), (3, 1, 0), (5, 2, 3), (4, 3, 0)])
+def test_adjoint_of_depthwise_convolution_is_convolution_with_flipped_taps(k, dilation, pad):
+    r = _rng(120 + k)
+    x = r.standard_normal((2, 3, 47), dtype=np.float32)
+    w = r.standard_normal((3, 1, k), dtype=np.float32)
+    y, _ = oracle.conv1d(x, w, 1, pad, dilation, 3)
+    g = r.standard_normal(y.shape).astype(np.float32)
+    span = (k - 1) * dilation
+    gx, _ = oracle.conv1d(g, w[:, :, ::-1].copy(), 1, span - pad, dilation, 3)           # A^T g
+    assert gx.shape == x.shape
+    assert abs(float((y * g).sum()) - float((x.astype(np.float64) * gx).sum())) < 1e-10
+
+
+def test_adjoint_of_dense_convolution_swaps_channels_and_flips_taps():
+    r = _rng(130)
+    x = r.standard_normal((2, 4, 29), dtype=np.float32)
+    w = r.standard_normal((5, 4, 3), dtype=np.float32)
+    y, _ = oracle.conv1d(x, w, 1, 1, 1, 1)
+    g = r.standard_normal(y.shape).astype(np.float32)
+    wt = np.ascontiguousarray(w.transpose(1, 0, 2)[:, :, ::-1])                          # [Cin, Cout, k], flipped
+    gx, _ = oracle.conv1d(g, wt, 1, 1, 1, 1)
+    assert abs(float((y * g).sum()) - float((x.astype(np.float64) * gx).sum())) < 1e-10
+    x2 = r.standard_normal((1, 3, 9, 8), dtype=np.float32)
+    w2 = r.standard_normal((2, 3, 3, 3), dtype=np.float32)
+    y2, _ = oracle.conv2d(x2, w2, 1, 1, 1, 1)
+    g2 = r.standard_normal(y2.shape).astype(np.float32)
+    wt2 = np.ascontiguousarray(w2.transpose(1, 0, 2, 3)[:, :, ::-1, ::-1])
+    gx2, _ = oracle.conv2d(g2, wt2, 1, 1, 1, 1)
+    assert abs(float((y2 * g2).sum()) - float((x2.astype(np.float64) * gx2).sum())) < 1e-10
