@@ -321,6 +321,7 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
     }
     const int b_lane = (pok ? (oh - oh_first) * g.sh * g.Wt + (ow - ow_first) * g.sw : 0) * XP + 4 * half;
     const int a_lane = (wm * 32 + l32) * XP + 4 * half;
+    const bool useful = co0 + wm * 32 < g.Cout;       // wave-uniform
 
     v16f acc;
 #pragma unroll
@@ -383,6 +384,7 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
         commit();
         __syncthreads();
         if (ci0 + CIB * NB < g.Cin) prefetch(ci0 + CIB * NB);   // in flight during the matrix work below
+        if (!useful) continue;                        // a block of 32 output channels beyond Cout: staging only
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             const float *Xb = Xl + nb * g.CP, *Wb = Wl + nb * wblock;
