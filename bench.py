@@ -350,10 +350,27 @@ def cpu_baseline(x_host, taps_host):
         oracle.conv1d(xs.reshape(slab // CH5, CH5, LEN5), taps_host, groups=CH5)
         nbytes += slide_bytes(slab, LEN5, K5) + 4 * CH5 * K5
     dt = time.perf_counter() - t0
-    return {"value": round(nbytes / dt / 1e9, 4), "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
+    cores = oracle.threads()
+    # per-core figure: the same seven operators on 1/64 of the rows with one thread
+    one = ROWS5 // 64
+    xs = xs_all[:one]
+    oracle.set_threads(1)
+    t1 = time.perf_counter()
+    nb1 = 0
+    for w in WINDOWS5:
+        oracle.slide1d(oracle.OP_ADD, xs, w)
+        oracle.slide1d(oracle.OP_MAX, xs, w)
+        nb1 += 2 * slide_bytes(one, LEN5, w)
+    oracle.conv1d(xs.reshape(one // CH5, CH5, LEN5), taps_host, groups=CH5)
+    nb1 += slide_bytes(one, LEN5, K5) + 4 * CH5 * K5
+    dt1 = time.perf_counter() - t1
+    oracle.set_threads(cores)
+    return {"value": round(nbytes / dt / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
             "seconds": round(dt, 3),
             "sample": "all 32768 rows of cfg5, all seven operators, i.e. one whole step "
-                      "(fp64 naive O(w*N), OpenMP over rows)"}
+                      "(fp64 naive O(w*N), OpenMP over rows)",
+            "single_core_GBps": round(nb1 / dt1 / 1e9, 4), "single_core_seconds": round(dt1, 3),
+            "single_core_sample": "first 512 rows, one thread"}
 
 
 def main():
@@ -405,18 +422,28 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    per = [0.0] * len(launches)
+    samples = [[] for _ in launches]               # ms per launch, one sample per step
     for k in range(args.steps):
         prev = ev0[k]
         for i in range(len(launches)):
-            per[i] += prev.elapsed_time(evs[k][i])
+            samples[i].append(prev.elapsed_time(evs[k][i]))
             prev = evs[k][i]
-    per = [p / args.steps for p in per]            # ms per launch
+    per = [sum(v) / len(v) for v in samples]       # mean ms per launch
     ms_step = wall * 1e3 / args.steps
+
+    # the ceiling of a one-read-one-write kernel on this device: a plain copy of the same 2 GiB
+    y_copy = outs[WINDOWS5[0]].view(-1)
+    n_copy = y_copy.numel()
+    copy_ms = time_launches(torch, lambda: B.sws_copy(x.view(-1)[:n_copy], y_copy), max(5, args.steps))
+    copy_gbps = 8.0 * n_copy / copy_ms / 1e6
 
     kernels = {}
     for (name, _, nb, fl), ms in zip(launches, per):
         rec = {"ms": round(ms, 4), "GBps": round(nb / ms / 1e6, 1), "frac_hbm_peak": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+        v = sorted(samples[len(kernels)])
+        rec["ms_median"] = round(v[len(v) // 2], 4)
+        rec["ms_min"] = round(v[0], 4)
+        rec["frac_copy_ceiling"] = round(nb / ms / 1e6 / copy_gbps, 4)
         if fl:
             rec["GFLOPs"] = round(fl / ms / 1e6, 1)
         kernels[name] = rec
@@ -455,10 +482,12 @@ def main():
         "pool_GBps": round(pool_bytes / slide_ms / 1e6, 1),
         "pool_frac_hbm_peak": round(pool_bytes / slide_ms / 1e6 / HBM_PEAK_GBPS, 4),
         "dwconv_GFLOPs": kernels["dwconv_k31"]["GFLOPs"],
+        "copy_ceiling": {"GBps": round(copy_gbps, 1), "frac_hbm_peak": round(copy_gbps / HBM_PEAK_GBPS, 4),
+                         "what": "sws_copy of 2 GiB -> 2 GiB, the same 128-bit strips with no arithmetic"},
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "avg_launch_ms": round(dom_ms, 4), "algorithmic_bytes_per_launch": dom_bytes,
-                     "traffic": traffic},
+                     "frac_of_copy_ceiling": round(achieved / copy_gbps, 4), "traffic": traffic},
         "kernels": kernels,
     }
     del outs, y_conv

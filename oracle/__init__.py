@@ -14,6 +14,7 @@ from .ref import (  # noqa: F401
     conv1d,
     conv2d,
     pool2d,
+    set_threads,
     PAD_EDGE,
     PAD_IDENTITY,
     PAD_MIRROR,

@@ -38,6 +38,8 @@ def _load():
         build(force=False)
         lib = ctypes.CDLL(_LIB)
         lib.sws_ref_threads.restype = ctypes.c_int
+        lib.sws_ref_set_threads.restype = None
+        lib.sws_ref_set_threads.argtypes = [ctypes.c_int]
         lib.sws_ref_slide1d.restype = ctypes.c_int
         lib.sws_ref_slide1d.argtypes = [ctypes.c_int, _fp, _dp, _dp, _i64, _i64, _i32, _f64]
         lib.sws_ref_pool2d.restype = ctypes.c_int
@@ -56,6 +58,11 @@ def _load():
                                        _i32, _i32, _i32, _i32, _i32, _i32]
         _lib = lib
     return _lib
+
+
+def set_threads(n):
+    """Threads the oracle's row loops use from now on (for a per-core timing)."""
+    _load().sws_ref_set_threads(int(n))
 
 
 def threads():

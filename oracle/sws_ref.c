@@ -68,6 +68,17 @@ int sws_ref_threads(void)
 #endif
 }
 
+/* Number of OpenMP threads for the calls that follow (timing the oracle on one core); no-op
+ * without OpenMP.  Has no effect on results. */
+void sws_ref_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 /* a (+) b with a the older (left) operand. */
 static double combine(int op, double a, double b)
 {
