@@ -1,0 +1,148 @@
+"""Seeded random sweeps of shapes against the oracle: row lengths around tile seams, row counts
+that move the output alignment, windows, pads, strides, dilations and channel counts drawn at
+random (fixed seeds, so every run sees the same cases)."""
+import numpy as np
+import pytest
+
+import oracle
+from parity_util import assert_bit_exact, assert_within_tol, to_gpu, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2305_16513_amd import binding
+    binding.lib()
+    return binding
+
+
+def _rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def _near_seams(r, w, lo_max=6000):
+    """An output length that sits on, just before or just after a multiple of the tile's outputs."""
+    tout = max(16, (1024 - (w - 1)) & ~15)
+    base = int(r.integers(1, max(2, lo_max // tout))) * tout
+    return max(1, base + int(r.integers(-20, 21)))
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_slide1d_random(B, seed):
+    r = _rng(7000 + seed)
+    w = int(r.choice([1, 2, 3, 4, 5, 7, 9, 15, 16, 17, 33, 64, 100, 255, 256, 511, 700, 850, 851, 961, 1100]))
+    lo = _near_seams(r, min(w, 961))
+    rows = int(r.integers(1, 9))
+    x = (r.random((rows, lo + w - 1), dtype=np.float32) * 2 - 1).astype(np.float32)
+    op = int(r.integers(0, 3))
+    scale = float(r.choice([1.0, 1.0 / w, 0.37]))
+    y = to_host(B.sws_slide1d(op, to_gpu(x), w, scale))
+    ref, mag = oracle.slide1d(op, x, w, scale)
+    what = "seed %d: op %d w %d rows %d lo %d" % (seed, op, w, rows, lo)
+    if op == 0:
+        assert_within_tol(y, ref, mag, what)
+    else:
+        assert_bit_exact(y, ref, what)
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_slide1d_padded_random(B, seed):
+    r = _rng(7100 + seed)
+    w = int(r.choice([1, 2, 3, 5, 8, 16, 31, 64, 255, 600, 961]))
+    length = int(r.integers(max(2, w // 2), 5000))
+    mode = int(r.integers(0, 4))
+    cap = length - 1 if mode == 1 else (length if mode == 2 else 2 * w)
+    pl, pr = int(r.integers(0, min(cap, 2 * w) + 1)), int(r.integers(0, min(cap, 2 * w) + 1))
+    if length + pl + pr < w:
+        pl = min(cap, w)
+        pr = min(cap, w)
+    if length + pl + pr < w:
+        pytest.skip("window longer than the extended row")
+    rows = int(r.integers(1, 6))
+    x = r.standard_normal((rows, length), dtype=np.float32)
+    op = int(r.integers(0, 3))
+    y = to_host(B.sws_slide1d_padded(op, to_gpu(x), w, pl, pr, mode, 0.5))
+    ref, mag = oracle.slide1d_padded(op, x, w, pl, pr, mode, 0.5)
+    what = "seed %d: op %d w %d len %d pads (%d,%d) mode %d" % (seed, op, w, length, pl, pr, mode)
+    if op == 0:
+        assert_within_tol(y, ref, mag, what)
+    else:
+        assert_bit_exact(y, ref, what)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_conv1d_random(B, seed):
+    r = _rng(7200 + seed)
+    kind = seed % 4
+    if kind == 0:                                   # depthwise / single channel, taps adjacent
+        c, mult, k, dil, stride = int(r.integers(1, 9)), int(r.integers(1, 3)), int(r.integers(1, 65)), 1, 1
+        cin, cout, groups = c, c * mult, c
+    elif kind == 1:                                 # depthwise, dilated
+        c, k, dil, stride = int(r.integers(1, 6)), int(r.integers(2, 40)), int(r.integers(2, 65)), 1
+        cin, cout, groups = c, c, c
+    elif kind == 2:                                 # dense on the matrix cores: strides, dilation, long kernels
+        cin, cout = 8 * int(r.integers(1, 9)), int(r.integers(1, 100))
+        k, dil, stride, groups = int(r.integers(1, 30)), int(r.integers(1, 5)), int(r.integers(1, 4)), 1
+    else:                                           # anything: grouped, odd channel counts, strides
+        groups = int(r.choice([1, 2, 3]))
+        cin, cout = groups * int(r.integers(1, 7)), groups * int(r.integers(1, 7))
+        k, dil, stride = int(r.integers(1, 12)), int(r.integers(1, 4)), int(r.integers(1, 4))
+    span = (k - 1) * dil + 1
+    pad = int(r.integers(0, span))
+    length = max(span - 2 * pad, 1) + int(r.integers(0, 3000))
+    x = r.standard_normal((int(r.integers(1, 4)), cin, length), dtype=np.float32)
+    w = (r.standard_normal((cout, cin // groups, k), dtype=np.float32) / np.sqrt(k * cin / groups)).astype(np.float32)
+    y = to_host(B.sws_conv1d(to_gpu(x), to_gpu(w), stride, pad, dil, groups))
+    ref, mag = oracle.conv1d(x, w, stride, pad, dil, groups)
+    assert_within_tol(y, ref, mag, "seed %d: %d->%d g%d k%d d%d s%d p%d L%d" % (seed, cin, cout, groups, k, dil, stride, pad, length))
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_pool2d_random(B, seed):
+    r = _rng(7300 + seed)
+    geoms = [(3, 3, 1, 1, 1, 1), (3, 3, 2, 2, 1, 1), (3, 3, 1, 1, 0, 0), (3, 3, 2, 2, 0, 0), (2, 2, 2, 2, 0, 0),
+             (2, 2, 1, 1, 0, 0), (5, 5, 1, 1, 2, 2), (5, 5, 1, 1, 0, 0), (7, 7, 1, 1, 3, 3), (9, 9, 1, 1, 4, 4),
+             (13, 13, 1, 1, 6, 6), (4, 3, 2, 1, 1, 2), (1, 7, 1, 3, 0, 3)]
+    kh, kw, sh, sw, ph, pw = geoms[int(r.integers(0, len(geoms)))]
+    h, w_ = int(r.integers(kh, 150)), int(r.integers(kw, 260))
+    x = r.standard_normal((int(r.integers(1, 3)), int(r.integers(1, 5)), h, w_), dtype=np.float32)
+    op = int(r.integers(0, 3))
+    y = to_host(B.sws_pool2d(op, to_gpu(x), kh, kw, sh, sw, ph, pw, 1.0 / (kh * kw)))
+    ref, mag = oracle.pool2d(op, x, kh, kw, sh, sw, ph, pw, 1.0 / (kh * kw))
+    what = "seed %d: op %d %dx%d s(%d,%d) p(%d,%d) on %dx%d" % (seed, op, kh, kw, sh, sw, ph, pw, h, w_)
+    if op == 0:
+        assert_within_tol(y, ref, mag, what)
+    else:
+        assert_bit_exact(y, ref, what)
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_conv2d_random(B, seed):
+    r = _rng(7400 + seed)
+    cin = int(r.choice([3, 4, 8, 12, 16, 24, 32, 64]))
+    cout = int(r.integers(1, 130))
+    kh, kw = int(r.integers(1, 8)), int(r.integers(1, 8))
+    sh, sw = int(r.integers(1, 4)), int(r.integers(1, 4))
+    ph, pw = int(r.integers(0, kh)), int(r.integers(0, kw))
+    h, w_ = int(r.integers(kh, 70)), int(r.integers(kw, 260))
+    x = r.standard_normal((int(r.integers(1, 4)), cin, h, w_), dtype=np.float32)
+    w = (r.standard_normal((cout, cin, kh, kw), dtype=np.float32) / np.sqrt(cin * kh * kw)).astype(np.float32)
+    y = to_host(B.sws_conv2d(to_gpu(x), to_gpu(w), sh, sw, ph, pw))
+    ref, mag = oracle.conv2d(x, w, sh, sw, ph, pw)
+    assert_within_tol(y, ref, mag, "seed %d: %d->%d %dx%d s(%d,%d) p(%d,%d) on %dx%d" % (seed, cin, cout, kh, kw, sh, sw, ph, pw, h, w_))
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_slide1d_pair_random(B, seed):
+    r = _rng(7500 + seed)
+    w = int(r.choice([1, 2, 3, 5, 16, 64, 255, 309, 310, 500, 961, 1000]))
+    length = w - 1 + int(r.integers(1, 4000))
+    rows = int(r.integers(1, 5))
+    u = ((1.0 + 0.03 * (2.0 * r.random((rows, length)) - 1.0)) * np.where(r.random((rows, length)) < 0.2, -1.0, 1.0)).astype(np.float32)
+    v = r.standard_normal((rows, length)).astype(np.float32)
+    yu, yv = B.sws_slide1d_pair(to_gpu(u), to_gpu(v), w)
+    ru, rv, mu, mv = oracle.slide1d_pair(u, v, w)
+    tol = (w + 24) * 2.0 ** -24
+    assert_within_tol(to_host(yu), ru, mu, "seed %d pair u w %d" % (seed, w), tol=tol)
+    assert_within_tol(to_host(yv), rv, mv, "seed %d pair v w %d" % (seed, w), tol=tol)
