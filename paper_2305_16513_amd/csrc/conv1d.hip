@@ -194,10 +194,14 @@ struct DilPlan {
     float inv_d, inv_16d;
 };
 
-template <int KB4>
+// MULTI: every output channel sums over the `cig` input channels of its group (few dense channels,
+// grouped convolution): the tile of each input channel is staged in turn and the taps of the
+// (output channel, input channel) pair are broadcast anew, all accumulating into the same
+// registers.  With MULTI the spacing d may be 1 (one phase).
+template <int KB4, bool MULTI>
 __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
     const float *__restrict__ x, const float *__restrict__ wgt, float *__restrict__ y, int L, int Lo, int k,
-    int pad, DilPlan pl, int Cin, int Cout, int cog, int tiles_per_row, int group, int chunks_per_row,
+    int pad, DilPlan pl, int Cin, int Cout, int cog, int cig, int tiles_per_row, int group, int chunks_per_row,
     int64_t n_units)
 {
     constexpr int K4 = 4 * KB4;
@@ -214,8 +218,8 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
     const int chunk = (int)(unit - ro * chunks_per_row);
     const int64_t b = ro / Cout;
     const int co = (int)(ro - b * Cout);
-    const float *xr = x + (b * Cin + co / cog) * (int64_t)L;
-    const float *wr = wgt + (int64_t)co * k;
+    const float *xg = x + (b * Cin + (int64_t)(co / cog) * cig) * (int64_t)L;     // first input channel of my group
+    const float *wr = wgt + (int64_t)co * cig * k;
     float *yr = y + ro * (int64_t)Lo;
     const int c = (int)((ro * Lo) & 15);             // 64-byte-aligned strip stores, as in the undilated kernel
     const int d = pl.d, MP = pl.MP, TO = pl.TO, NI = pl.NI;
@@ -240,12 +244,15 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
 
     // Taps: one coalesced load (lane t holds tap t, zero beyond k), then broadcast into scalar registers.
     float f[K4];
-    {
-        float tv = wr[lane < k ? lane : 0];
-        tv = lane < k ? tv : 0.0f;
+    auto load_taps = [&](int ci) {
+        const float tv = wr[ci * k + (lane < k ? lane : 0)];
+        return lane < k ? tv : 0.0f;
+    };
+    auto spread_taps = [&](float tv) {
 #pragma unroll
         for (int t = 0; t < K4; ++t) f[t] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(tv), t));
-    }
+    };
+    if (!MULTI) spread_taps(load_taps(0));
 
     const int ph = lane / pl.G, gl = lane - ph * pl.G;
     const bool active = lane < d * pl.G;
@@ -265,6 +272,16 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
     for (int t = chunk * group + wave; t < t_end; t += kWavesPerWg) {
         const int t0 = t * TO - c;
         const int p0 = t0 - pad;                     // global index of tile input 0
+        float acc[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
+        float tv_next = MULTI ? load_taps(0) : 0.0f;
+        for (int ci = 0; ci < (MULTI ? cig : 1); ++ci) {
+        const float *xr = xg + (int64_t)ci * L;
+        if (MULTI) {
+            spread_taps(tv_next);
+            tv_next = load_taps(ci + 1 < cig ? ci + 1 : ci);       // in flight during this channel's work
+        }
         // ---- stage: coalesced strips -> phase-major LDS, four strips in flight at a time
         for (int j0 = 0; j0 < n_strips; j0 += 4) {
             v4f g4[4];
@@ -314,14 +331,12 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
             const v4f g = *(const v4f *)(A + wbase + 4 * u + 4 * (u >> 2));
             xw[4 * u] = g.x; xw[4 * u + 1] = g.y; xw[4 * u + 2] = g.z; xw[4 * u + 3] = g.w;
         }
-        float acc[16];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
 #pragma unroll
         for (int tt = 0; tt < K4; ++tt)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[e] = fmaf(f[tt], xw[e + tt], acc[e]);
-        wave_lds_sync();
+        wave_lds_sync();                             // every lane has its window: the slice may be reused
+        }
         // ---- outputs p + d*(16 gl + e) -> LDS -> strips
         if (active) {
             int o = obase;
@@ -353,7 +368,7 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
 // Tile geometry of the dilated kernel; false if the tile does not fit a wavefront's LDS slice.
 bool plan_dilated(int d, int K4, DilPlan *pl)
 {
-    if (d < 2 || d > kDilMaxD) return false;
+    if (d < 1 || d > kDilMaxD) return false;
     pl->d = d;
     pl->G = 64 / d;
     const int M = 16 * pl->G + K4;                   // staged indices per phase
@@ -372,7 +387,7 @@ bool plan_dilated(int d, int K4, DilPlan *pl)
 
 template <int KB4>
 hipError_t launch_thin_dilated(const float *x, const float *wgt, float *y, int64_t rows_out, int L, int Lo, int k,
-                               int pad, const DilPlan &pl, int Cin, int Cout, int cog, hipStream_t s)
+                               int pad, const DilPlan &pl, int Cin, int Cout, int cog, int cig, hipStream_t s)
 {
     const int tiles_per_row = (Lo + 15 + pl.TO - 1) / pl.TO;
     int64_t g = (KB4 <= 8 ? 4 : 8) * kWavesPerWg;    // the scatter table is built once per workgroup
@@ -385,12 +400,31 @@ hipError_t launch_thin_dilated(const float *x, const float *wgt, float *y, int64
     const int64_t grid = xcd_grid(n_units);
     if (grid > 2147483647LL) return hipErrorInvalidValue;
     const size_t lds_bytes = ((size_t)pl.tab_strips * 256 + (size_t)kWavesPerWg * pl.slice) * sizeof(float);
-    hipLaunchKernelGGL((conv1d_thin_dilated_kernel<KB4>), dim3((unsigned)grid), dim3(kThreads), lds_bytes, s, x, wgt,
-                       y, L, Lo, k, pad, pl, Cin, Cout, cog, tiles_per_row, group, chunks_per_row, n_units);
+    if (cig > 1)
+        hipLaunchKernelGGL((conv1d_thin_dilated_kernel<KB4, true>), dim3((unsigned)grid), dim3(kThreads), lds_bytes, s,
+                           x, wgt, y, L, Lo, k, pad, pl, Cin, Cout, cog, cig, tiles_per_row, group, chunks_per_row,
+                           n_units);
+    else
+        hipLaunchKernelGGL((conv1d_thin_dilated_kernel<KB4, false>), dim3((unsigned)grid), dim3(kThreads), lds_bytes, s,
+                           x, wgt, y, L, Lo, k, pad, pl, Cin, Cout, cog, 1, tiles_per_row, group, chunks_per_row,
+                           n_units);
     return hipGetLastError();
 }
 
 constexpr int kThinMaxK = 64;
+
+// Dense channels: the vector-ALU kernel against the matrix-core kernel.  Measured on
+// x[64, C, 16384], C -> C channels (TFLOP/s, vector ALU / matrix cores): k = 51: 52 / 11 (C = 8),
+// 58 / 27 (16), 61 / 56 (32), 63 / 87 (64); k = 9: 16 / 11, 23 / 27, 27 / 62, 29 / 101; k = 3:
+// 7 / 6, 11 / 19, 13 / 43, 14 / 89.  The vector-ALU rate depends on the taps per staged tile,
+// the matrix rate on how much of its 64-channel tile the output channels fill.
+bool prefer_few(int64_t Cin, int64_t Cout, int k)
+{
+    if (Cin % 8 != 0) return true;                   // the matrix kernel stages 8 input channels at a time
+    const double mfma_est = 1.6 * (double)(Cout < 64 ? Cout : 64);
+    const double valu_est = k >= 24 ? 55.0 : (k >= 12 ? 35.0 : (k >= 6 ? 22.0 : 11.0));
+    return valu_est > 1.05 * mfma_est;
+}
 
 }  // namespace
 
@@ -399,21 +433,30 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
                          int32_t groups, hipStream_t s)
 {
     int variant = g_opt.conv1d_variant;
-    const bool thin_ok = (Cin / groups == 1) && stride == 1 && dilation == 1 && k <= kThinMaxK;
+    const int cig = (int)(Cin / groups);
+    const bool thin_ok = cig == 1 && stride == 1 && dilation == 1 && k <= kThinMaxK;
     const bool dense_ok = groups == 1 && Cin >= 2;
     DilPlan dpl;
-    const bool thin_dil_ok = (Cin / groups == 1) && stride == 1 && dilation > 1 && k <= kThinMaxK && L >= 4 &&
-                             plan_dilated(dilation, 4 * ((k + 3) / 4), &dpl);
+    const bool plan_ok = stride == 1 && k <= kThinMaxK && L >= 4 && (cig > 1 || dilation > 1) &&
+                         plan_dilated(dilation, 4 * ((k + 3) / 4), &dpl);
+    const bool thin_dil_ok = cig == 1 && plan_ok;
+    const bool few_ok = cig > 1 && plan_ok;          // a few input channels per output channel, on the vector ALU
     if (variant == 2 && !thin_ok) variant = 0;
     if (variant == 4 && !thin_dil_ok) variant = 0;
     if (variant == 3 && !dense_ok) variant = 0;
-    if (variant == 0) variant = thin_ok ? 2 : (thin_dil_ok ? 4 : (dense_ok ? 3 : 1));
+    if (variant == 6 && !few_ok) variant = 0;
+    if (variant == 0) {
+        if (thin_ok) variant = 2;
+        else if (thin_dil_ok) variant = 4;
+        else if (dense_ok && !(few_ok && prefer_few(Cin, Cout, k))) variant = 3;
+        else variant = few_ok ? 6 : 1;
+    }
     if (variant == 3) {
         // the dense contraction is the 2-D kernel on images of height 1
         bool taken = false;
         const hipError_t e = launch_conv2d_mfma(x, wgt, y, B, Cin, 1, L, Cout, 1, Lo, 1, k, 1, stride, 0, pad, 1, dilation, s, &taken);
         if (taken) return e;
-        variant = 1;
+        variant = few_ok ? 6 : 1;
     }
     if (variant == 2) {
         const int cog = (int)(Cout / groups);
@@ -428,11 +471,11 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
         }
 #undef SWS_THIN
     }
-    if (variant == 4) {
+    if (variant == 4 || variant == 6) {
         const int cog = (int)(Cout / groups);
 #define SWS_THIN_DIL(KB)                                                                                        \
     case KB:                                                                                                    \
-        return launch_thin_dilated<KB>(x, wgt, y, B * Cout, (int)L, (int)Lo, k, pad, dpl, (int)Cin, (int)Cout, cog, s)
+        return launch_thin_dilated<KB>(x, wgt, y, B * Cout, (int)L, (int)Lo, k, pad, dpl, (int)Cin, (int)Cout, cog, cig, s)
         switch ((k + 3) / 4) {
             SWS_THIN_DIL(1); SWS_THIN_DIL(2); SWS_THIN_DIL(3); SWS_THIN_DIL(4); SWS_THIN_DIL(5); SWS_THIN_DIL(6);
             SWS_THIN_DIL(7); SWS_THIN_DIL(8); SWS_THIN_DIL(9); SWS_THIN_DIL(10); SWS_THIN_DIL(11); SWS_THIN_DIL(12);

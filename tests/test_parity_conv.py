@@ -187,6 +187,26 @@ def test_conv1d_dense_dilated_and_long_kernels(B, cin, cout, k, dilation, pad, s
     _c1(B, x, w, stride=stride, pad=pad, dilation=dilation, what="dense k=%d d=%d" % (k, dilation))
 
 
+@pytest.mark.parametrize("cin,cout,groups,k,dilation,pad", [
+    (15, 15, 1, 51, 8, 200),      # odd channel counts, long dilated kernel: the vector-ALU kernel sums over input channels
+    (3, 5, 1, 7, 1, 3),
+    (12, 8, 4, 9, 2, 5),          # grouped: three input channels per output channel
+    (16, 16, 1, 31, 1, 15),       # few dense channels, many taps
+    (6, 6, 2, 64, 1, 0),
+    (10, 4, 2, 2, 64, 10),
+])
+def test_conv1d_few_channels_on_the_vector_alu(B, cin, cout, groups, k, dilation, pad):
+    r = _rng(cin * 3 + cout + groups + k)
+    x = r.standard_normal((3, cin, 2600), dtype=np.float32)
+    w = (r.standard_normal((cout, cin // groups, k), dtype=np.float32) * np.sqrt(2.0 / (cin // groups * k))).astype(np.float32)
+    for variant in (0, 6, 1):
+        B.sws_set_option("conv1d_variant", variant)
+        try:
+            _c1(B, x, w, pad=pad, dilation=dilation, groups=groups, what="few %d->%d g%d k%d d%d variant %d" % (cin, cout, groups, k, dilation, variant))
+        finally:
+            B.sws_set_option("conv1d_variant", 0)
+
+
 @pytest.mark.parametrize("stride,k,pad", [(2, 3, 1), (3, 5, 2), (2, 1, 0), (4, 9, 4)])
 def test_conv1d_dense_strided(B, stride, k, pad):
     r = _rng(stride * 10 + k)
