@@ -69,8 +69,11 @@ __global__ __launch_bounds__(kPer == 8 ? 256 : 128) void slide_generic_kernel(co
                                                                  const float *__restrict__ x1,
                                                                  float *__restrict__ y0, float *__restrict__ y1,
                                                                  int len, int lo, int S, int tout, int tiles_per_row,
-                                                                 int64_t n_tiles, float scale, float inv_S)
+                                                                 int64_t n_tiles, float scale, float inv_S, int pitch,
+                                                                 int accum)
 {
+    // Rows are `pitch` apart and `len` of their elements are used; with `accum` the result is combined
+    // with what y already holds (an earlier link of a chain of windows, which covers older elements).
     constexpr int NP = O::NP;
     constexpr int kTile = 64 * kPer, kWavesPerWg = kPer == 8 ? 4 : 2;
     // planes [0, NP): the inputs, later Pre; planes [NP, 2 NP): Suf.  One private slice per wavefront.
@@ -82,7 +85,7 @@ __global__ __launch_bounds__(kPer == 8 ? 256 : 128) void slide_generic_kernel(co
     if (gt >= n_tiles) return;                       // whole wavefronts leave; no workgroup barrier below
     const int64_t r = gt / tiles_per_row;
     const int t0 = (int)(gt - r * tiles_per_row) * tout;
-    const float *xr[2] = {x0 + r * (int64_t)len, NP > 1 ? x1 + r * (int64_t)len : nullptr};
+    const float *xr[2] = {x0 + r * (int64_t)pitch, NP > 1 ? x1 + r * (int64_t)pitch : nullptr};
     float *yr[2] = {y0 + r * (int64_t)lo, NP > 1 ? y1 + r * (int64_t)lo : nullptr};
     float(*L)[kTile] = lds[wave];
 
@@ -238,6 +241,14 @@ __global__ __launch_bounds__(kPer == 8 ? 256 : 128) void slide_generic_kernel(co
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             O::f(a4[c], b4[c], o4[c]);
+            if (accum && q + c < lim) {
+                float old[NP], t2[NP];
+#pragma unroll
+                for (int p = 0; p < NP; ++p) old[p] = yr[p][t0 + q + c];
+                O::f(old, o4[c], t2);
+#pragma unroll
+                for (int p = 0; p < NP; ++p) o4[c][p] = t2[p];
+            }
             if (O::kScaled) o4[c][0] *= scale;
         }
 #pragma unroll
@@ -253,8 +264,7 @@ __global__ __launch_bounds__(kPer == 8 ? 256 : 128) void slide_generic_kernel(co
     }
 }
 
-// One thread per output, the window folded left to right: windows the tile kernels do not
-// cover (w = 1, w > 961).
+// One thread per output, the window folded left to right: w = 1.
 template <class O>
 __global__ __launch_bounds__(256) void slide_generic_direct_kernel(const float *__restrict__ x0,
                                                                     const float *__restrict__ x1,
@@ -283,24 +293,46 @@ __global__ __launch_bounds__(256) void slide_generic_direct_kernel(const float *
 }
 
 template <class O>
+hipError_t launch_generic_tiles(const float *x0, const float *x1, float *y0, float *y1, int64_t rows, int len, int lo,
+                                int w, float scale, int pitch, int accum, hipStream_t s)
+{
+    const bool small = w <= kSmallMaxW;
+    const int S = w - 1, tout = (small ? 512 : 1024) - S, waves = small ? 4 : 2;
+    const int64_t tiles_per_row = (lo + tout - 1) / tout;
+    const int64_t n_tiles = rows * tiles_per_row;
+    const int64_t grid = (n_tiles + waves - 1) / waves;
+    if (grid > 2147483647LL) return hipErrorInvalidValue;
+    if (small)
+        hipLaunchKernelGGL((slide_generic_kernel<O, 8>), dim3((unsigned)grid), dim3(256), 0, s, x0, x1, y0, y1, len, lo, S,
+                           tout, (int)tiles_per_row, n_tiles, scale, 1.0f / (float)S, pitch, accum);
+    else
+        hipLaunchKernelGGL((slide_generic_kernel<O, 16>), dim3((unsigned)grid), dim3(128), 0, s, x0, x1, y0, y1, len, lo, S,
+                           tout, (int)tiles_per_row, n_tiles, scale, 1.0f / (float)S, pitch, accum);
+    return hipGetLastError();
+}
+
+template <class O>
 hipError_t launch_generic(const float *x0, const float *x1, float *y0, float *y1, int64_t rows, int64_t len, int32_t w,
                           float scale, hipStream_t s)
 {
     const int64_t lo = len - w + 1;
-    if (w >= 2 && w <= kGenericMaxW) {
-        const bool small = w <= kSmallMaxW;
-        const int S = w - 1, tout = (small ? 512 : 1024) - S, waves = small ? 4 : 2;
-        const int64_t tiles_per_row = (lo + tout - 1) / tout;
-        const int64_t n_tiles = rows * tiles_per_row;
-        const int64_t grid = (n_tiles + waves - 1) / waves;
-        if (grid > 2147483647LL) return hipErrorInvalidValue;
-        if (small)
-            hipLaunchKernelGGL((slide_generic_kernel<O, 8>), dim3((unsigned)grid), dim3(256), 0, s, x0, x1, y0, y1,
-                               (int)len, (int)lo, S, tout, (int)tiles_per_row, n_tiles, scale, 1.0f / (float)S);
-        else
-            hipLaunchKernelGGL((slide_generic_kernel<O, 16>), dim3((unsigned)grid), dim3(128), 0, s, x0, x1, y0, y1,
-                               (int)len, (int)lo, S, tout, (int)tiles_per_row, n_tiles, scale, 1.0f / (float)S);
-        return hipGetLastError();
+    if (w >= 2 && w <= kGenericMaxW)
+        return launch_generic_tiles<O>(x0, x1, y0, y1, rows, (int)len, (int)lo, w, scale, (int)len, 0, s);
+    if (w > kGenericMaxW) {
+        // A chain of shorter windows, w = w_0 + w_1 + ...:  y[i] = Y_0[i] (+) Y_1[i + w_0] (+) ...
+        // (associativity; links oldest first, so the operand order holds).
+        const int links = (w + 767) / 768;
+        int done = 0;
+        for (int j = 0; j < links; ++j) {
+            const int wj = (w - done) / (links - j);
+            const bool last = j == links - 1;
+            const hipError_t e = launch_generic_tiles<O>(x0 + done, O::NP > 1 ? x1 + done : nullptr, y0, y1, rows,
+                                                         (int)lo + wj - 1, (int)lo, wj, last ? scale : 1.0f, (int)len,
+                                                         j > 0, s);
+            if (e != hipSuccess) return e;
+            done += wj;
+        }
+        return hipSuccess;
     }
     const int64_t grid = (rows * lo + 255) / 256;
     if (grid > 2147483647LL) return hipErrorInvalidValue;

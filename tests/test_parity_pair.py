@@ -43,7 +43,7 @@ def _check(B, u, v, w, what):
     return max(a, b)
 
 
-@pytest.mark.parametrize("w", [1, 2, 3, 4, 5, 8, 16, 17, 64, 255, 309, 310, 449, 600, 961, 962, 1500])
+@pytest.mark.parametrize("w", [1, 2, 3, 4, 5, 8, 16, 17, 64, 255, 309, 310, 449, 600, 961, 962, 1500, 2500])
 @pytest.mark.parametrize("length", [64, 700, 1500, 4099])
 def test_pair_windows_and_ragged_lengths(B, w, length):
     if w > length:
@@ -53,7 +53,7 @@ def test_pair_windows_and_ragged_lengths(B, w, length):
     _check(B, u, v, w, "w=%d len=%d" % (w, length))
 
 
-@pytest.mark.parametrize("w", [2, 7, 64, 255, 700])
+@pytest.mark.parametrize("w", [2, 7, 64, 255, 700, 2000])
 def test_pair_exact_on_signs_and_small_integers(B, w):
     """u in {-1, +1}, v small integers: every partial result is exact in fp32, so the GPU must
     agree bit for bit whatever its association order — and the order of operands must be right."""
