@@ -192,6 +192,8 @@ constexpr int kDilMaxD = 64;
 struct DilPlan {
     int d, G, MP, slice, TO, NI, tab_strips;
     float inv_d, inv_16d;
+    int wstride, wofs, accum;                        // a chunk of a longer kernel: taps per channel pair in memory,
+                                                     // first tap of this launch, add to what y already holds
 };
 
 // MULTI: every output channel sums over the `cig` input channels of its group (few dense channels,
@@ -219,7 +221,7 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
     const int64_t b = ro / Cout;
     const int co = (int)(ro - b * Cout);
     const float *xg = x + (b * Cin + (int64_t)(co / cog) * cig) * (int64_t)L;     // first input channel of my group
-    const float *wr = wgt + (int64_t)co * cig * k;
+    const float *wr = wgt + (int64_t)co * cig * pl.wstride + pl.wofs;
     float *yr = y + ro * (int64_t)Lo;
     const int c = (int)((ro * Lo) & 15);             // 64-byte-aligned strip stores, as in the undilated kernel
     const int d = pl.d, MP = pl.MP, TO = pl.TO, NI = pl.NI;
@@ -245,7 +247,7 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
     // Taps: one coalesced load (lane t holds tap t, zero beyond k), then broadcast into scalar registers.
     float f[K4];
     auto load_taps = [&](int ci) {
-        const float tv = wr[ci * k + (lane < k ? lane : 0)];
+        const float tv = wr[ci * pl.wstride + (lane < k ? lane : 0)];
         return lane < k ? tv : 0.0f;
     };
     auto spread_taps = [&](float tv) {
@@ -351,14 +353,15 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
         for (int j = 0; j < 4; ++j) {
             const int q = j * 256 + 4 * lane;
             if (q >= lim) continue;
-            const v4f o = *(const v4f *)(A + rpos[j]);
+            v4f o = *(const v4f *)(A + rpos[j]);
             if (q >= qlo && q + 4 <= lim) {
+                if (pl.accum) o += *(const v4f_u *)(yr + t0 + q);
                 __builtin_nontemporal_store(o, (v4f_u *)(yr + t0 + q));
             } else {
-                if (q + 0 >= qlo && q + 0 < lim) yr[t0 + q + 0] = o.x;
-                if (q + 1 >= qlo && q + 1 < lim) yr[t0 + q + 1] = o.y;
-                if (q + 2 >= qlo && q + 2 < lim) yr[t0 + q + 2] = o.z;
-                if (q + 3 >= qlo && q + 3 < lim) yr[t0 + q + 3] = o.w;
+                if (q + 0 >= qlo && q + 0 < lim) yr[t0 + q + 0] = pl.accum ? yr[t0 + q + 0] + o.x : o.x;
+                if (q + 1 >= qlo && q + 1 < lim) yr[t0 + q + 1] = pl.accum ? yr[t0 + q + 1] + o.y : o.y;
+                if (q + 2 >= qlo && q + 2 < lim) yr[t0 + q + 2] = pl.accum ? yr[t0 + q + 2] + o.z : o.z;
+                if (q + 3 >= qlo && q + 3 < lim) yr[t0 + q + 3] = pl.accum ? yr[t0 + q + 3] + o.w : o.w;
             }
         }
         wave_lds_sync();
@@ -382,6 +385,9 @@ bool plan_dilated(int d, int K4, DilPlan *pl)
     pl->tab_strips = ((pl->NI + 255) / 256 + 3) & ~3;
     pl->inv_d = 1.0f / (float)d;
     pl->inv_16d = 1.0f / (float)(16 * d);
+    pl->wstride = 0;
+    pl->wofs = 0;
+    pl->accum = 0;
     return pl->slice <= kDilSliceMax;
 }
 
@@ -436,9 +442,12 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
     const int cig = (int)(Cin / groups);
     const bool thin_ok = cig == 1 && stride == 1 && dilation == 1 && k <= kThinMaxK;
     const bool dense_ok = groups == 1 && Cin >= 2;
+    // The phase-major kernel: taps spaced apart, several input channels per output channel, and — as
+    // a chain of launches over chunks of at most 64 taps, each adding to y — kernels of any length.
+    const int k_chunk = k <= kThinMaxK ? k : kThinMaxK;
     DilPlan dpl;
-    const bool plan_ok = stride == 1 && k <= kThinMaxK && L >= 4 && (cig > 1 || dilation > 1) &&
-                         plan_dilated(dilation, 4 * ((k + 3) / 4), &dpl);
+    const bool plan_ok = stride == 1 && L >= 4 && (cig > 1 || dilation > 1 || k > kThinMaxK) &&
+                         plan_dilated(dilation, 4 * ((k_chunk + 3) / 4), &dpl);
     const bool thin_dil_ok = cig == 1 && plan_ok;
     const bool few_ok = cig > 1 && plan_ok;          // a few input channels per output channel, on the vector ALU
     if (variant == 2 && !thin_ok) variant = 0;
@@ -473,16 +482,30 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
     }
     if (variant == 4 || variant == 6) {
         const int cog = (int)(Cout / groups);
+        const int n_chunks = (k + kThinMaxK - 1) / kThinMaxK;
+        for (int c = 0; c < n_chunks; ++c) {
+            const int first = c * kThinMaxK, kc = (k - first < kThinMaxK) ? k - first : kThinMaxK;
+            DilPlan pc = dpl;
+            pc.wstride = k;
+            pc.wofs = first;
+            pc.accum = c > 0;
+            const int pad_c = pad - first * dilation;           // the chunk's first tap sits first * dilation further on
+            hipError_t e = hipErrorInvalidValue;
 #define SWS_THIN_DIL(KB)                                                                                        \
     case KB:                                                                                                    \
-        return launch_thin_dilated<KB>(x, wgt, y, B * Cout, (int)L, (int)Lo, k, pad, dpl, (int)Cin, (int)Cout, cog, cig, s)
-        switch ((k + 3) / 4) {
-            SWS_THIN_DIL(1); SWS_THIN_DIL(2); SWS_THIN_DIL(3); SWS_THIN_DIL(4); SWS_THIN_DIL(5); SWS_THIN_DIL(6);
-            SWS_THIN_DIL(7); SWS_THIN_DIL(8); SWS_THIN_DIL(9); SWS_THIN_DIL(10); SWS_THIN_DIL(11); SWS_THIN_DIL(12);
-            SWS_THIN_DIL(13); SWS_THIN_DIL(14); SWS_THIN_DIL(15); SWS_THIN_DIL(16);
-        default: break;
-        }
+        e = launch_thin_dilated<KB>(x, wgt, y, B * Cout, (int)L, (int)Lo, kc, pad_c, pc, (int)Cin, (int)Cout, cog,  \
+                                    cig, s);                                                                    \
+        break
+            switch ((kc + 3) / 4) {
+                SWS_THIN_DIL(1); SWS_THIN_DIL(2); SWS_THIN_DIL(3); SWS_THIN_DIL(4); SWS_THIN_DIL(5); SWS_THIN_DIL(6);
+                SWS_THIN_DIL(7); SWS_THIN_DIL(8); SWS_THIN_DIL(9); SWS_THIN_DIL(10); SWS_THIN_DIL(11);
+                SWS_THIN_DIL(12); SWS_THIN_DIL(13); SWS_THIN_DIL(14); SWS_THIN_DIL(15); SWS_THIN_DIL(16);
+            default: break;
+            }
 #undef SWS_THIN_DIL
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
     }
     return launch_conv1d_naive(x, wgt, y, B, Cin, L, Cout, Lo, k, stride, pad, dilation, groups, s);
 }

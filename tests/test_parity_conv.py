@@ -207,6 +207,17 @@ def test_conv1d_few_channels_on_the_vector_alu(B, cin, cout, groups, k, dilation
             B.sws_set_option("conv1d_variant", 0)
 
 
+@pytest.mark.parametrize("cin,cout,groups,k,dilation,pad", [
+    (4, 4, 4, 65, 1, 0), (4, 8, 4, 127, 1, 63), (2, 2, 2, 200, 1, 10), (3, 3, 3, 70, 3, 100), (6, 4, 2, 80, 1, 7),
+    (5, 3, 1, 129, 2, 128),
+])
+def test_conv1d_kernels_longer_than_64_taps_run_as_chunks(B, cin, cout, groups, k, dilation, pad):
+    r = _rng(cin + cout * 5 + k)
+    x = r.standard_normal((2, cin, 3500), dtype=np.float32)
+    w = (r.standard_normal((cout, cin // groups, k), dtype=np.float32) / np.sqrt(cin // groups * k)).astype(np.float32)
+    _c1(B, x, w, pad=pad, dilation=dilation, groups=groups, what="long k=%d d=%d g=%d" % (k, dilation, groups))
+
+
 @pytest.mark.parametrize("stride,k,pad", [(2, 3, 1), (3, 5, 2), (2, 1, 0), (4, 9, 4)])
 def test_conv1d_dense_strided(B, stride, k, pad):
     r = _rng(stride * 10 + k)
