@@ -200,7 +200,12 @@ struct DilPlan {
 // grouped convolution): the tile of each input channel is staged in turn and the taps of the
 // (output channel, input channel) pair are broadcast anew, all accumulating into the same
 // registers.  With MULTI the spacing d may be 1 (one phase).
-template <int KB4, bool MULTI>
+//
+// STRIDED (taps adjacent, outputs `d` inputs apart — here d is the stride): the staged tile is
+// phase-major in the same way, but now a lane's 16 consecutive outputs draw on every phase: output
+// i, tap r + j*d reads phase r at index i + j.  So the lane walks the phases, each with its own
+// window and its own taps (every d-th tap from r on); KB4 then counts the taps of ONE phase.
+template <int KB4, bool MULTI, bool STRIDED>
 __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
     const float *__restrict__ x, const float *__restrict__ wgt, float *__restrict__ y, int L, int Lo, int k,
     int pad, DilPlan pl, int Cin, int Cout, int cog, int cig, int tiles_per_row, int group, int chunks_per_row,
@@ -254,18 +259,32 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
 #pragma unroll
         for (int t = 0; t < K4; ++t) f[t] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(tv), t));
     };
-    if (!MULTI) spread_taps(load_taps(0));
+    // every d-th tap from r on (strided mode): phase r's taps
+    auto spread_phase_taps = [&](float tv, int r) {
+#pragma unroll
+        for (int j = 0; j < K4; ++j) {
+            const int idx = r + j * d;               // wave-uniform
+            const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(tv), idx < 64 ? idx : 63));
+            f[j] = idx < k ? v : 0.0f;
+        }
+    };
+    float tv_one = 0.0f;                             // the tap vector when there is one input channel
+    if (!MULTI) {
+        tv_one = load_taps(0);
+        if (!STRIDED) spread_taps(tv_one);
+    }
 
-    const int ph = lane / pl.G, gl = lane - ph * pl.G;
-    const bool active = lane < d * pl.G;
+    const int ph = STRIDED ? 0 : lane / pl.G, gl = STRIDED ? lane : lane - ph * pl.G;
+    const bool active = STRIDED ? lane < pl.G : lane < d * pl.G;
     const int wbase = active ? ph * MP + 20 * gl : 0;
-    const int obase = ph + (16 * d + 4) * gl;        // my outputs on their way back: obase + d*e
+    const int obase = STRIDED ? 20 * lane : ph + (16 * d + 4) * gl;   // my outputs on their way back
     const int n_strips = (NI + 255) >> 8;
     int rpos[4];                                     // my strip groups on their way out
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int q = j * 256 + 4 * lane;
-        rpos[j] = q < TO ? q + 4 * (int)(((float)q + 0.5f) * pl.inv_16d) : 0;
+        if (STRIDED) rpos[j] = q < TO ? q + 4 * (q >> 4) : 0;
+        else rpos[j] = q < TO ? q + 4 * (int)(((float)q + 0.5f) * pl.inv_16d) : 0;
     }
     __syncthreads();                                 // table complete
 
@@ -273,15 +292,17 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
     if (t_end > tiles_per_row) t_end = tiles_per_row;
     for (int t = chunk * group + wave; t < t_end; t += kWavesPerWg) {
         const int t0 = t * TO - c;
-        const int p0 = t0 - pad;                     // global index of tile input 0
+        const int p0 = (STRIDED ? t0 * d : t0) - pad;    // global index of tile input 0
         float acc[16];
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
         float tv_next = MULTI ? load_taps(0) : 0.0f;
         for (int ci = 0; ci < (MULTI ? cig : 1); ++ci) {
         const float *xr = xg + (int64_t)ci * L;
+        float tv_cur = tv_one;
         if (MULTI) {
-            spread_taps(tv_next);
+            tv_cur = tv_next;
+            if (!STRIDED) spread_taps(tv_cur);
             tv_next = load_taps(ci + 1 < cig ? ci + 1 : ci);       // in flight during this channel's work
         }
         // ---- stage: coalesced strips -> phase-major LDS, four strips in flight at a time
@@ -326,21 +347,28 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
             }
         }
         wave_lds_sync();
-        // ---- my window: phase ph, indices 16*gl .. 16*gl + K4 + 15
-        float xw[K4 + 16];
+        // ---- my window: phase ph, indices 16*gl .. 16*gl + K4 + 15 (strided: every phase in turn)
+        for (int r = 0; r < (STRIDED ? d : 1); ++r) {
+            if (STRIDED) spread_phase_taps(tv_cur, r);
+            float xw[K4 + 16];
 #pragma unroll
-        for (int u = 0; u < NG; ++u) {
-            const v4f g = *(const v4f *)(A + wbase + 4 * u + 4 * (u >> 2));
-            xw[4 * u] = g.x; xw[4 * u + 1] = g.y; xw[4 * u + 2] = g.z; xw[4 * u + 3] = g.w;
+            for (int u = 0; u < NG; ++u) {
+                const v4f g = *(const v4f *)(A + wbase + r * MP + 4 * u + 4 * (u >> 2));
+                xw[4 * u] = g.x; xw[4 * u + 1] = g.y; xw[4 * u + 2] = g.z; xw[4 * u + 3] = g.w;
+            }
+#pragma unroll
+            for (int tt = 0; tt < K4; ++tt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[e] = fmaf(f[tt], xw[e + tt], acc[e]);
         }
-#pragma unroll
-        for (int tt = 0; tt < K4; ++tt)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[e] = fmaf(f[tt], xw[e + tt], acc[e]);
         wave_lds_sync();                             // every lane has its window: the slice may be reused
         }
         // ---- outputs p + d*(16 gl + e) -> LDS -> strips
-        if (active) {
+        if (STRIDED) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                *(v4f *)(A + obase + 4 * u) = (v4f){acc[4 * u], acc[4 * u + 1], acc[4 * u + 2], acc[4 * u + 3]};
+        } else if (active) {
             int o = obase;
 #pragma unroll
             for (int e = 0; e < 16; ++e) { A[o] = acc[e]; o += d; }
@@ -391,9 +419,40 @@ bool plan_dilated(int d, int K4, DilPlan *pl)
     return pl->slice <= kDilSliceMax;
 }
 
+// Tile geometry of the strided mode: `s` phases of the staged input, as many lanes (16 outputs each)
+// as fit the slice; K4 = taps of one phase, padded to a multiple of 4.
+bool plan_strided(int s, int K4, DilPlan *pl)
+{
+    if (s < 2 || s > kDilMaxD) return false;
+    int nl = 64;
+    int MP = 0;
+    for (; nl >= 4; --nl) {
+        const int M = 16 * nl + K4;
+        MP = M + 4 * ((M + 15) / 16);
+        if (((MP / 4) & 1) == 0) MP += 4;
+        if (s * MP + 64 <= kDilSliceMax) break;
+    }
+    if (nl < 4) return false;
+    pl->d = s;
+    pl->G = nl;                                      // active lanes
+    pl->MP = MP;
+    pl->TO = 16 * nl;
+    pl->NI = s * (16 * nl + K4);
+    const int out_floats = 1344;                     // 64 lanes x 20 floats + a strip's reach
+    pl->slice = (s * MP > out_floats ? s * MP : out_floats) + 64;
+    pl->tab_strips = ((pl->NI + 255) / 256 + 3) & ~3;
+    pl->inv_d = 1.0f / (float)s;
+    pl->inv_16d = 0.0f;
+    pl->wstride = 0;
+    pl->wofs = 0;
+    pl->accum = 0;
+    return pl->slice <= kDilSliceMax + 64;
+}
+
 template <int KB4>
 hipError_t launch_thin_dilated(const float *x, const float *wgt, float *y, int64_t rows_out, int L, int Lo, int k,
-                               int pad, const DilPlan &pl, int Cin, int Cout, int cog, int cig, hipStream_t s)
+                               int pad, const DilPlan &pl, int Cin, int Cout, int cog, int cig, hipStream_t s,
+                               bool strided = false)
 {
     const int tiles_per_row = (Lo + 15 + pl.TO - 1) / pl.TO;
     int64_t g = (KB4 <= 8 ? 4 : 8) * kWavesPerWg;    // the scatter table is built once per workgroup
@@ -406,14 +465,18 @@ hipError_t launch_thin_dilated(const float *x, const float *wgt, float *y, int64
     const int64_t grid = xcd_grid(n_units);
     if (grid > 2147483647LL) return hipErrorInvalidValue;
     const size_t lds_bytes = ((size_t)pl.tab_strips * 256 + (size_t)kWavesPerWg * pl.slice) * sizeof(float);
-    if (cig > 1)
-        hipLaunchKernelGGL((conv1d_thin_dilated_kernel<KB4, true>), dim3((unsigned)grid), dim3(kThreads), lds_bytes, s,
-                           x, wgt, y, L, Lo, k, pad, pl, Cin, Cout, cog, cig, tiles_per_row, group, chunks_per_row,
-                           n_units);
-    else
-        hipLaunchKernelGGL((conv1d_thin_dilated_kernel<KB4, false>), dim3((unsigned)grid), dim3(kThreads), lds_bytes, s,
-                           x, wgt, y, L, Lo, k, pad, pl, Cin, Cout, cog, 1, tiles_per_row, group, chunks_per_row,
-                           n_units);
+#define SWS_DIL_LAUNCH(MULTI, STRIDED)                                                                          \
+    hipLaunchKernelGGL((conv1d_thin_dilated_kernel<KB4, MULTI, STRIDED>), dim3((unsigned)grid), dim3(kThreads),  \
+                       lds_bytes, s, x, wgt, y, L, Lo, k, pad, pl, Cin, Cout, cog, cig, tiles_per_row, group,    \
+                       chunks_per_row, n_units)
+    if (strided) {
+        if (cig > 1) SWS_DIL_LAUNCH(true, true);
+        else SWS_DIL_LAUNCH(false, true);
+    } else {
+        if (cig > 1) SWS_DIL_LAUNCH(true, false);
+        else SWS_DIL_LAUNCH(false, false);
+    }
+#undef SWS_DIL_LAUNCH
     return hipGetLastError();
 }
 
@@ -450,22 +513,44 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
                          plan_dilated(dilation, 4 * ((k_chunk + 3) / 4), &dpl);
     const bool thin_dil_ok = cig == 1 && plan_ok;
     const bool few_ok = cig > 1 && plan_ok;          // a few input channels per output channel, on the vector ALU
+    // strides (taps adjacent): the same kernel walking the phases of the input
+    DilPlan spl;
+    const int k_phase = (k + stride - 1) / stride;                 // taps of one phase
+    const bool strided_ok = stride > 1 && dilation == 1 && k <= kThinMaxK && L >= 4 &&
+                            plan_strided(stride, 4 * ((k_phase + 3) / 4), &spl);
     if (variant == 2 && !thin_ok) variant = 0;
     if (variant == 4 && !thin_dil_ok) variant = 0;
     if (variant == 3 && !dense_ok) variant = 0;
     if (variant == 6 && !few_ok) variant = 0;
+    if (variant == 7 && !strided_ok) variant = 0;
+    const bool valu_ok = few_ok || (strided_ok && cig > 1);
     if (variant == 0) {
         if (thin_ok) variant = 2;
         else if (thin_dil_ok) variant = 4;
-        else if (dense_ok && !(few_ok && prefer_few(Cin, Cout, k))) variant = 3;
-        else variant = few_ok ? 6 : 1;
+        else if (dense_ok && !(valu_ok && prefer_few(Cin, Cout, k))) variant = 3;
+        else variant = few_ok ? 6 : (strided_ok ? 7 : 1);
     }
     if (variant == 3) {
         // the dense contraction is the 2-D kernel on images of height 1
         bool taken = false;
         const hipError_t e = launch_conv2d_mfma(x, wgt, y, B, Cin, 1, L, Cout, 1, Lo, 1, k, 1, stride, 0, pad, 1, dilation, s, &taken);
         if (taken) return e;
-        variant = few_ok ? 6 : 1;
+        variant = few_ok ? 6 : (strided_ok ? 7 : 1);
+    }
+    if (variant == 7) {
+        const int cog = (int)(Cout / groups);
+        spl.wstride = k;
+#define SWS_THIN_STR(KB)                                                                                        \
+    case KB:                                                                                                    \
+        return launch_thin_dilated<KB>(x, wgt, y, B * Cout, (int)L, (int)Lo, k, pad, spl, (int)Cin, (int)Cout, cog, \
+                                       cig, s, true)
+        switch ((k_phase + 3) / 4) {
+            SWS_THIN_STR(1); SWS_THIN_STR(2); SWS_THIN_STR(3); SWS_THIN_STR(4); SWS_THIN_STR(5); SWS_THIN_STR(6);
+            SWS_THIN_STR(7); SWS_THIN_STR(8);
+        default: break;
+        }
+#undef SWS_THIN_STR
+        variant = 1;
     }
     if (variant == 2) {
         const int cog = (int)(Cout / groups);

@@ -218,6 +218,27 @@ def test_conv1d_kernels_longer_than_64_taps_run_as_chunks(B, cin, cout, groups, 
     _c1(B, x, w, pad=pad, dilation=dilation, groups=groups, what="long k=%d d=%d g=%d" % (k, dilation, groups))
 
 
+@pytest.mark.parametrize("cin,cout,groups,k,stride,pad", [
+    (1, 64, 1, 10, 5, 0),         # one input channel fanned out to many, stride 5 (a raw-waveform front end)
+    (6, 6, 6, 3, 2, 1),           # depthwise, stride 2
+    (4, 8, 4, 7, 3, 3),
+    (12, 8, 4, 9, 2, 4),          # grouped, three input channels per output channel
+    (5, 7, 1, 64, 7, 10),         # odd dense channels, long kernel, stride 7
+    (3, 3, 3, 2, 64, 0),          # stride larger than the kernel
+    (2, 2, 2, 5, 17, 2),
+])
+def test_conv1d_strided_thin_and_grouped(B, cin, cout, groups, k, stride, pad):
+    r = _rng(cin * 7 + cout + k * 3 + stride)
+    x = r.standard_normal((3, cin, 5000), dtype=np.float32)
+    w = (r.standard_normal((cout, cin // groups, k), dtype=np.float32) / np.sqrt(cin // groups * k)).astype(np.float32)
+    for variant in (0, 7, 1):
+        B.sws_set_option("conv1d_variant", variant)
+        try:
+            _c1(B, x, w, stride=stride, pad=pad, groups=groups, what="strided %d->%d g%d k%d s%d variant %d" % (cin, cout, groups, k, stride, variant))
+        finally:
+            B.sws_set_option("conv1d_variant", 0)
+
+
 @pytest.mark.parametrize("stride,k,pad", [(2, 3, 1), (3, 5, 2), (2, 1, 0), (4, 9, 4)])
 def test_conv1d_dense_strided(B, stride, k, pad):
     r = _rng(stride * 10 + k)
