@@ -487,12 +487,18 @@ constexpr int kThinMaxK = 64;
 // 58 / 27 (16), 61 / 56 (32), 63 / 87 (64); k = 9: 16 / 11, 23 / 27, 27 / 62, 29 / 101; k = 3:
 // 7 / 6, 11 / 19, 13 / 43, 14 / 89.  The vector-ALU rate depends on the taps per staged tile,
 // the matrix rate on how much of its 64-channel tile the output channels fill.
-bool prefer_few(int64_t Cin, int64_t Cout, int k)
+// With stride 2 the vector-ALU kernel has half the taps per staged phase: k = 51: 36-44, k = 31:
+// 29-38, k = 9: 6-8, k = 3: 2-3, against 10 / 24 / 52 / 80 on the matrix cores for C = 8 / 16 / 32 / 64.
+bool prefer_few(int64_t Cin, int64_t Cout, int k, bool strided)
 {
     if (Cin % 8 != 0) return true;                   // the matrix kernel stages 8 input channels at a time
-    const double mfma_est = 1.6 * (double)(Cout < 64 ? Cout : 64);
+    const double cm = (double)(Cout < 64 ? Cout : 64);
+    if (strided) {
+        const double valu_est = k >= 40 ? 38.0 : (k >= 24 ? 31.0 : (k >= 12 ? 14.0 : (k >= 6 ? 7.0 : 2.5)));
+        return valu_est > 1.05 * 1.5 * cm;
+    }
     const double valu_est = k >= 24 ? 55.0 : (k >= 12 ? 35.0 : (k >= 6 ? 22.0 : 11.0));
-    return valu_est > 1.05 * mfma_est;
+    return valu_est > 1.05 * 1.6 * cm;
 }
 
 }  // namespace
@@ -527,7 +533,7 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
     if (variant == 0) {
         if (thin_ok) variant = 2;
         else if (thin_dil_ok) variant = 4;
-        else if (dense_ok && !(valu_ok && prefer_few(Cin, Cout, k))) variant = 3;
+        else if (dense_ok && !(valu_ok && prefer_few(Cin, Cout, k, stride > 1))) variant = 3;
         else variant = few_ok ? 6 : (strided_ok ? 7 : 1);
     }
     if (variant == 3) {
