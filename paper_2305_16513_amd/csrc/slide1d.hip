@@ -4,9 +4,9 @@
 //
 //  * slide_direct_kernel: the Vector Slide idea of Section 3 (Algorithm 4) — the output
 //    vector is the (+) of w shifted copies of the input vector.  A lane owns four consecutive
-//    outputs and reads its shifted operands as 128-bit loads at +4, +8 elements.  The
-//    re-read lines cost more than the scan below even at w = 2 (measured), so it is the
-//    default only for w = 1 (a scaled copy) and otherwise an A/B variant for w <= 9.
+//    outputs and reads its shifted operands as 128-bit loads at +4, +8 elements.  Used for
+//    w = 1 (a scaled copy) and for w <= 9 on short rows or small problems; on long rows of
+//    large inputs the scan below is 3-6 % faster even at w = 2 (measured).
 //
 //  * slide_scan_kernel (every w >= 2): the block form of the Vector Input algorithm
 //    (Section 3, Algorithm 2).  A wavefront owns a tile of 64*C consecutive inputs cut
@@ -42,82 +42,61 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-struct TilePlan {
-    int tiles_per_row;     // wave tiles along one row
-    int tout;              // outputs per wave tile
-    int group;             // consecutive tiles of a row handled by one workgroup
-    int chunks_per_row;    // workgroups per row
-    int64_t n_units;       // rows * chunks_per_row
-};
-
-TilePlan plan_tiles(int64_t rows, int lo, int max_tout)
-{
-    TilePlan p;
-    p.tiles_per_row = (lo + max_tout - 1) / max_tout;
-    p.tout = (lo + p.tiles_per_row - 1) / p.tiles_per_row;
-    const int64_t total = rows * p.tiles_per_row;
-    int64_t g = total / 2048;                      // aim for >= 8 workgroups per CU ...
-    if (g < kWavesPerWg) g = kWavesPerWg;          // ... but at least one tile per wavefront
-    if (g > p.tiles_per_row) g = p.tiles_per_row;
-    p.group = (int)g;
-    p.chunks_per_row = (p.tiles_per_row + p.group - 1) / p.group;
-    p.n_units = rows * p.chunks_per_row;
-    return p;
-}
-
 // ------------------------------------------------------------------------------------------
 // Small windows: y[i] = x[i] (+) x[i+1] (+) ... (+) x[i+W-1] from shifted 128-bit loads.
 // ------------------------------------------------------------------------------------------
 template <int OP, int W>
 __global__ __launch_bounds__(kThreads) void slide_direct_kernel(const float *__restrict__ x,
                                                                 float *__restrict__ y, int len, int lo,
-                                                                float scale, int tiles_per_row, int group,
-                                                                int chunks_per_row, int64_t n_units)
+                                                                float scale, int tiles_per_row, int64_t n_tiles,
+                                                                int remap)
 {
     using O = Op<OP>;
     constexpr int NV = (W + 2) / 4 + 1;            // float4 groups covering x[q .. q+W+2]
-    const int64_t unit = xcd_unit(n_units);
+    // One 1024-output tile per wavefront, tiles numbered over all rows; four consecutive tiles per
+    // workgroup (the tiles in flight then stay a compact window of memory).
+    const int64_t n_units = (n_tiles + kWavesPerWg - 1) / kWavesPerWg;
+    const int64_t unit = remap ? xcd_unit(n_units) : (int64_t)blockIdx.x;
     if (unit < 0) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t r = unit / chunks_per_row;
-    const int chunk = (int)(unit - r * chunks_per_row);
+    const int64_t gt = unit * kWavesPerWg + wave;
+    if (gt >= n_tiles) return;
+    const int64_t r = gt / tiles_per_row;
+    const int t = (int)(gt - r * tiles_per_row);
     const float *xr = x + r * (int64_t)len;
     float *yr = y + r * (int64_t)lo;
-    int t_end = (chunk + 1) * group;
-    if (t_end > tiles_per_row) t_end = tiles_per_row;
-
-    for (int t = chunk * group + wave; t < t_end; t += kWavesPerWg) {
+    // tile origins pulled back so that every 1 KB strip store starts on a 64-byte line of y
+    const int t0 = t * 1024 - (int)((r * lo) & 15);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int q = t * 1024 + j * 256 + 4 * lane;     // first of this lane's four outputs
-            if (q >= lo) continue;
-            float a[4 * NV];
-            if (q <= len - 4 * NV) {
+    for (int j = 0; j < 4; ++j) {
+        const int q = t0 + j * 256 + 4 * lane;       // first of this lane's four outputs
+        if (q >= lo || q + 4 <= 0) continue;
+        float a[4 * NV];
+        if (q >= 0 && q <= len - 4 * NV) {
 #pragma unroll
-                for (int u = 0; u < NV; ++u) {
-                    const v4f g = *(const v4f_u *)(xr + q + 4 * u);
-                    a[4 * u] = g.x; a[4 * u + 1] = g.y; a[4 * u + 2] = g.z; a[4 * u + 3] = g.w;
-                }
-            } else {
-#pragma unroll
-                for (int u = 0; u < 4 * NV; ++u) a[u] = (q + u < len) ? xr[q + u] : O::id();
+            for (int u = 0; u < NV; ++u) {
+                const v4f g = *(const v4f_u *)(xr + q + 4 * u);
+                a[4 * u] = g.x; a[4 * u + 1] = g.y; a[4 * u + 2] = g.z; a[4 * u + 3] = g.w;
             }
-            float o[4];
+        } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float acc = a[e];
+            for (int u = 0; u < 4 * NV; ++u) a[u] = (q + u >= 0 && q + u < len) ? xr[q + u] : O::id();
+        }
+        float o[4];
 #pragma unroll
-                for (int s = 1; s < W; ++s) acc = O::f(acc, a[e + s]);
-                o[e] = (OP == SWS_OP_ADD) ? acc * scale : acc;
-            }
-            if (q + 4 <= lo) {
-                const v4f g = {o[0], o[1], o[2], o[3]};
-                __builtin_nontemporal_store(g, (v4f_u *)(yr + q));
-            } else {
+        for (int e = 0; e < 4; ++e) {
+            float acc = a[e];
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (q + e < lo) yr[q + e] = o[e];
-            }
+            for (int s = 1; s < W; ++s) acc = O::f(acc, a[e + s]);
+            o[e] = (OP == SWS_OP_ADD) ? acc * scale : acc;
+        }
+        if (q >= 0 && q + 4 <= lo) {
+            const v4f g = {o[0], o[1], o[2], o[3]};
+            __builtin_nontemporal_store(g, (v4f_u *)(yr + q));
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (q + e >= 0 && q + e < lo) yr[q + e] = o[e];
         }
     }
 }
@@ -269,18 +248,30 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
                 *(v4f *)(A + strip_pos + 256 * j) = *(const v4f_u *)(xt + q);
             }
         } else {
+            // a tile at an end of its row: strip by strip (wave-uniform tests) — whole strips inside
+            // the row are still 128-bit loads, strips wholly outside hold the identity
+            v4f g4[NS];
 #pragma unroll
             for (int j = 0; j < NS; ++j) {
                 const int q = j * 256 + 4 * lane;
-                float e4[4];
+                const int s0 = t0 - pad_left + j * 256;          // physical index of the strip's first element
+                if (s0 >= 0 && s0 + 256 <= len) {
+                    g4[j] = *(const v4f_u *)(xt + q);
+                } else if (!PADDED && (s0 >= len || s0 + 256 <= 0)) {
+                    g4[j] = (v4f){O::id(), O::id(), O::id(), O::id()};
+                } else {
+                    float e4[4];
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const int e = t0 + q + c;        // element of the extended row
-                    const int src = (e >= 0 && e < lv) ? pad_src(e, len, pad_left, pad_mode) : -1;
-                    e4[c] = src >= 0 ? xr[src] : O::id();
+                    for (int c = 0; c < 4; ++c) {
+                        const int e = t0 + q + c;    // element of the extended row
+                        const int src = (e >= 0 && e < lv) ? pad_src(e, len, pad_left, pad_mode) : -1;
+                        e4[c] = src >= 0 ? xr[src] : O::id();
+                    }
+                    g4[j] = (v4f){e4[0], e4[1], e4[2], e4[3]};
                 }
-                *(v4f *)(A + strip_pos + 256 * j) = (v4f){e4[0], e4[1], e4[2], e4[3]};
             }
+#pragma unroll
+            for (int j = 0; j < NS; ++j) *(v4f *)(A + strip_pos + 256 * j) = g4[j];
         }
         wave_lds_sync();
         // ---- my chunk of C consecutive elements
@@ -379,13 +370,16 @@ template <int OP>
 hipError_t launch_direct(const float *x, float *y, int64_t rows, int len, int lo, int w, float scale,
                          hipStream_t s)
 {
-    const TilePlan p = plan_tiles(rows, lo, 1024);
-    const int64_t grid = xcd_grid(p.n_units);
+    const int tiles_per_row = (lo + 15 + 1023) / 1024;          // origins move back by up to 15
+    const int64_t n_tiles = rows * tiles_per_row;
+    const int64_t n_units = (n_tiles + kWavesPerWg - 1) / kWavesPerWg;
+    const int remap = (g_opt.slide_chunk & 8) ? 0 : 1;
+    const int64_t grid = remap ? xcd_grid(n_units) : n_units;
     if (grid > 2147483647LL) return hipErrorInvalidValue;
 #define SWS_DIRECT(WV)                                                                                     \
     case WV:                                                                                               \
         hipLaunchKernelGGL((slide_direct_kernel<OP, WV>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, \
-                           len, lo, scale, p.tiles_per_row, p.group, p.chunks_per_row, p.n_units);         \
+                           len, lo, scale, tiles_per_row, n_tiles, remap);                                 \
         break
     switch (w) {
         SWS_DIRECT(1); SWS_DIRECT(2); SWS_DIRECT(3); SWS_DIRECT(4); SWS_DIRECT(5);
@@ -493,8 +487,14 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
     // Measured on 16384-long rows: beyond w = 850 two links of half the width beat one pass whose
     // tiles are mostly halo.
     if (variant == 0) {
+        // Windows up to 9 on short rows (every fifth tile of a 4096-long row is a border tile of
+        // the scan kernel) or on small problems (latency-bound: fewer phases per tile): the
+        // shifted-load kernel.  Measured, max, 2 GiB: 4096-long rows 0.76 ms against 0.79-0.82;
+        // 16384-long rows 0.76-0.77 against 0.73-0.76; cfg 1 in a HIP graph 3.0-3.4 us against 4.3.
+        const bool small_w = w <= kDirectMaxW && (lo <= 8192 || rows * len64 <= (8LL << 20));
         if (w == 1) variant = padded ? 1 : 2;
         else if (padded) variant = w <= kScanMaxW ? 3 : 1;
+        else if (small_w) variant = 2;
         else variant = w <= kChainMinW ? 3 : 5;
     }
     if (variant == 5) {                              // longer than a tile: a chain of windows
