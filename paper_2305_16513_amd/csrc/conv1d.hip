@@ -86,13 +86,22 @@ __global__ __launch_bounds__(kThreads, (KB4 <= 8 ? 5 : 4)) void conv1d_thin_kern
             for (int j = 0; j < 4; ++j) g[j] = *(const v4f_u *)(xr + p0 + j * 256 + 4 * lane);
             g[4] = (4 * lane < K4) ? *(const v4f_u *)(xr + p0 + kTileOut + 4 * lane) : (v4f){0.0f, 0.0f, 0.0f, 0.0f};
         } else {
+            // a tile at an end of its row: strip by strip (wave-uniform tests) — whole strips inside
+            // the row are still 128-bit loads, strips wholly outside are zero
 #pragma unroll
             for (int j = 0; j < 5; ++j) {
-                const int p = p0 + j * 256 + 4 * lane;
-                g[j].x = (p + 0 >= 0 && p + 0 < L) ? xr[p + 0] : 0.0f;
-                g[j].y = (p + 1 >= 0 && p + 1 < L) ? xr[p + 1] : 0.0f;
-                g[j].z = (p + 2 >= 0 && p + 2 < L) ? xr[p + 2] : 0.0f;
-                g[j].w = (p + 3 >= 0 && p + 3 < L) ? xr[p + 3] : 0.0f;
+                const int s0 = p0 + j * 256;
+                const int p = s0 + 4 * lane;
+                if (s0 >= 0 && s0 + 256 <= L) {
+                    g[j] = *(const v4f_u *)(xr + p);
+                } else if (s0 >= L || s0 + 256 <= 0) {
+                    g[j] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+                } else {
+                    g[j].x = (p + 0 >= 0 && p + 0 < L) ? xr[p + 0] : 0.0f;
+                    g[j].y = (p + 1 >= 0 && p + 1 < L) ? xr[p + 1] : 0.0f;
+                    g[j].z = (p + 2 >= 0 && p + 2 < L) ? xr[p + 2] : 0.0f;
+                    g[j].w = (p + 3 >= 0 && p + 3 < L) ? xr[p + 3] : 0.0f;
+                }
             }
         }
     };
