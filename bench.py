@@ -182,7 +182,8 @@ def sweeps_table(torch, B, workloads, iters=20):
     plus a batched depthwise form that fills the device).  GB/s on algorithmic bytes, TFLOP/s on
     2*k FLOP per output; the vector-ALU peak without packed fp32 is 78.6 TFLOP/s."""
     g = lambda a: torch.from_numpy(a).cuda()
-    out = {"filter_sweep": {}, "dilated_single": {}, "dilated_batched": {}, "pair_operator": {}, "same_size_pooling": {}}
+    out = {"filter_sweep": {}, "dilated_single": {}, "dilated_batched": {}, "pair_operator": {}, "same_size_pooling": {},
+           "storage_16bit": {}}
     c6 = workloads.CONFIGS[6]
     rows, length = c6.x_shape[0], c6.x_shape[2]
     x6 = g(workloads.make(6)[0])
@@ -254,6 +255,22 @@ def sweeps_table(torch, B, workloads, iters=20):
             del y
     del u, v
     torch.cuda.empty_cache()
+    # configuration 5's sliding sums on 16-bit storage (fp32 arithmetic, one rounding): half the bytes
+    x16 = g(workloads.make(5)[0]).to(torch.bfloat16)
+    for dt, dn in ((torch.bfloat16, "bf16"), (torch.float16, "f16")):
+        xs = x16 if dt == torch.bfloat16 else x16.to(dt)
+        for op, opn in ((0, "add"), (1, "max")):
+            for w in WINDOWS5 if dn == "bf16" else (64,):
+                y = torch.empty(256, 128, LEN5 - w + 1, device="cuda", dtype=dt)
+                ms = time_launches(torch, lambda: B.sws_slide1d_16(op, xs, w, 1.0 / w, y=y), iters)
+                nb = slide_bytes(ROWS5, LEN5, w) // 2
+                out["storage_16bit"]["%s_%s_w%d" % (dn, opn, w)] = {
+                    "ms": round(ms, 4), "GBps": round(nb / ms / 1e6, 1), "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                    "Gelem_per_s": round(ROWS5 * (LEN5 - w + 1) / ms / 1e6, 1)}
+                del y
+        del xs
+    del x16
+    torch.cuda.empty_cache()
     return out
 
 
@@ -264,6 +281,13 @@ def run_only(torch, B, workloads, name, steps):
         src = torch.rand(ROWS5, LEN5, device="cuda")
         dst = torch.empty_like(src)
         fn = lambda: B.sws_copy(src, dst)
+    elif name.startswith("slide16_"):                     # slide16_<bf16|f16>_<add|max>_w<w>
+        _, dn, opn, wn = name.split("_")
+        w = int(wn[1:])
+        dt = torch.bfloat16 if dn == "bf16" else torch.float16
+        x = g(workloads.make(5)[0]).to(dt)
+        y = torch.empty(256, 128, LEN5 - w + 1, device="cuda", dtype=dt)
+        fn = lambda: B.sws_slide1d_16(0 if opn == "add" else 1, x, w, 1.0 / w, y=y)
     elif name.startswith("slide_") or name == "dwconv_k31":
         x_host, taps_host = workloads.make(5)
         x = g(x_host)

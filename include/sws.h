@@ -78,6 +78,24 @@ sws_status sws_slide1d_padded(sws_op op, const float *x, float *y, int64_t rows,
                               int32_t w, int32_t pad_left, int32_t pad_right, sws_pad_mode mode,
                               float scale, void *stream);
 
+/* Storage types of sws_slide1d_16.  Arithmetic is fp32 for both. */
+typedef enum {
+    SWS_DTYPE_BF16 = 1,        /* 1 sign, 8 exponent, 7 fraction bits (the upper half of an fp32) */
+    SWS_DTYPE_F16 = 2          /* IEEE 754 binary16 */
+} sws_dtype;
+
+/* sws_slide1d on 16-bit storage: the input quantised to fewer bits (the paper's introduction
+ * names quantisation as the way to shrink what a layer moves; Eq. 3 itself is unchanged).
+ * x and y hold bf16 or fp16 elements; each element is widened to fp32 exactly, the window is
+ * combined in fp32 as in sws_slide1d, multiplied by scale (ADD), and rounded to the storage
+ * type once, to nearest even.  MAX / MIN results are therefore exact.  Half the bytes of the
+ * fp32 entry point cross HBM.
+ *   x : device, rows*len 16-bit elements     y : device, rows*(len-w+1) 16-bit elements
+ *   (2-byte aligned; densely packed)
+ * Errors: as sws_slide1d, and INVALID_ARG for an unknown dtype. */
+sws_status sws_slide1d_16(sws_op op, sws_dtype dtype, const void *x, void *y, int64_t rows,
+                          int64_t len, int32_t w, float scale, void *stream);
+
 /* Sliding window sum (Eq. 3) under the pair operator of Section 2.4, Eq. 8 — the associative,
  * NON-commutative operator with which the paper writes a dot product as a prefix sum:
  *

@@ -7,6 +7,8 @@ wrapper that does argument marshalling only.  It imports nothing from the GPU
 package and the GPU package imports nothing from here.
 """
 from .ref import (  # noqa: F401
+    DTYPE_BF16,
+    DTYPE_F16,
     OP_ADD,
     OP_MAX,
     OP_MIN,
@@ -14,6 +16,7 @@ from .ref import (  # noqa: F401
     conv1d,
     conv2d,
     pool2d,
+    round16,
     set_threads,
     PAD_EDGE,
     PAD_IDENTITY,

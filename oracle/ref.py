@@ -50,6 +50,8 @@ def _load():
                                                ctypes.c_int, _f64]
         lib.sws_ref_slide1d_pair.restype = ctypes.c_int
         lib.sws_ref_slide1d_pair.argtypes = [_fp, _fp, _dp, _dp, _dp, _dp, _i64, _i64, _i32]
+        lib.sws_ref_round16.restype = ctypes.c_int
+        lib.sws_ref_round16.argtypes = [_dp, _dp, _i64, ctypes.c_int]
         lib.sws_ref_conv1d.restype = ctypes.c_int
         lib.sws_ref_conv1d.argtypes = [_fp, _fp, _dp, _dp, _i64, _i64, _i64, _i64,
                                        _i32, _i32, _i32, _i32, _i32]
@@ -100,6 +102,18 @@ def slide1d(op, x, w, scale=1.0):
     if rc:
         raise ValueError("sws_ref_slide1d rejected its arguments")
     return y, s
+
+
+DTYPE_BF16, DTYPE_F16 = 1, 2
+
+
+def round16(y, dtype):
+    """float64 array -> float64 array holding the nearest bf16 / fp16 values (ties to even)."""
+    y = np.ascontiguousarray(y, dtype=np.float64)
+    out = np.empty_like(y)
+    if _load().sws_ref_round16(_ptr_d(y), _ptr_d(out), y.size, dtype):
+        raise ValueError("sws_ref_round16 rejected its arguments")
+    return out
 
 
 PAD_IDENTITY, PAD_MIRROR, PAD_PERIODIC, PAD_EDGE = 0, 1, 2, 3

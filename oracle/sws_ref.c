@@ -26,6 +26,10 @@
  *   sws_ref_slide1d_pair  Eq. 3 with the pair operator of Section 2.4, Eq. 8:
  *                    (u_i, v_i) (+) (u_j, v_j) = (u_i*u_j, u_j*v_i + v_j), i older.
  *                    Non-commutative; folded strictly left to right.
+ *   sws_ref_round16  the value of the bf16 / fp16 number nearest to a double (ties to the even
+ *                    significand, overflow to infinity): how a result computed on 16-bit
+ *                    storage (the quantised inputs the paper's introduction mentions) is
+ *                    written back.  The 16-bit sliding sum is round16(slide1d(widened x)).
  *   sws_ref_conv1d   Section 2.5 (convolution = sliding dot product, Eq. 4 per
  *   sws_ref_conv2d   output): cross-correlation (no tap flip), zero padding by
  *                    skipping out-of-range taps, accumulation order ci, kh, kw.
@@ -48,7 +52,8 @@
  * separability of pooling, strided = subsampled); for the pair operator a
  * hand-folded case, u = 1 (sliding add of v), v = 0 (sliding product of u),
  * exact rational arithmetic on small integers, order sensitivity, and the
- * Eq. 7 sequence whose full-length window yields the dot product.
+ * Eq. 7 sequence whose full-length window yields the dot product; for round16 the
+ * library's own fp16 / bf16 casts, hand-written ties, subnormals and overflow.
  */
 #include <math.h>
 #include <stddef.h>
@@ -307,5 +312,32 @@ int sws_ref_slide1d_padded(int op, const float *x, double *y, double *abs_sum, i
             if (abs_sum) abs_sum[r * lo + i] = op == REF_ADD ? mag * fabs(scale) : mag;
         }
     }
+    return 0;
+}
+
+/* Nearest number with `frac_bits` fraction bits whose smallest normal exponent is min_exp:
+ * spacing 2^(e - frac_bits) in the binade of v (the smallest normal's spacing below it),
+ * rint() rounds ties to even in the default rounding mode, anything beyond the largest finite
+ * value becomes infinity. */
+static double round_to_format(double v, int frac_bits, int min_exp, double max_finite)
+{
+    if (v == 0.0 || !isfinite(v)) return v;
+    int e;
+    (void)frexp(fabs(v), &e);                 /* |v| = m * 2^e with m in [0.5, 1): leading bit 2^(e-1) */
+    int lead = e - 1;
+    if (lead < min_exp) lead = min_exp;
+    const double ulp = ldexp(1.0, lead - frac_bits);
+    const double r = rint(v / ulp) * ulp;     /* division and product by a power of two are exact */
+    return fabs(r) > max_finite ? copysign(INFINITY, v) : r;
+}
+
+/* dtype 1 = bf16 (7 fraction bits, exponents of fp32), 2 = fp16 (10 fraction bits, smallest
+ * normal 2^-14, largest finite 65504). */
+int sws_ref_round16(const double *in, double *out, int64_t n, int dtype)
+{
+    if (n < 0 || (dtype != 1 && dtype != 2) || (n > 0 && (!in || !out))) return 1;
+    for (int64_t i = 0; i < n; ++i)
+        out[i] = dtype == 1 ? round_to_format(in[i], 7, -126, ldexp(2.0 - ldexp(1.0, -7), 127))
+                            : round_to_format(in[i], 10, -14, 65504.0);
     return 0;
 }

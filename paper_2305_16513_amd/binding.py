@@ -19,7 +19,7 @@ _lib = None
 
 _i64, _i32, _f32, _vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
 
-EXPORTS = ("sws_slide1d", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_conv1d", "sws_conv2d", "sws_copy", "sws_out_len",
+EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_conv1d", "sws_conv2d", "sws_copy", "sws_out_len",
            "sws_status_string", "sws_set_option", "sws_version")
 
 
@@ -39,6 +39,8 @@ def lib():
         L = ctypes.CDLL(LIB_PATH)
         L.sws_slide1d.restype = ctypes.c_int
         L.sws_slide1d.argtypes = [ctypes.c_int, _vp, _vp, _i64, _i64, _i32, _f32, _vp]
+        L.sws_slide1d_16.restype = ctypes.c_int
+        L.sws_slide1d_16.argtypes = [ctypes.c_int, ctypes.c_int, _vp, _vp, _i64, _i64, _i32, _f32, _vp]
         L.sws_slide1d_padded.restype = ctypes.c_int
         L.sws_slide1d_padded.argtypes = [ctypes.c_int, _vp, _vp, _i64, _i64, _i32, _i32, _i32, ctypes.c_int, _f32, _vp]
         L.sws_slide1d_pair.restype = ctypes.c_int
@@ -121,6 +123,32 @@ def sws_slide1d(op, x, w, scale=1.0, y=None, stream=None):
     y = _out(y, tuple(x.shape[:-1]) + (lo,), x)
     _check(lib().sws_slide1d(op, x.data_ptr(), y.data_ptr(), rows, length, w, scale, _stream(stream)),
            "sws_slide1d")
+    return y
+
+
+SWS_DTYPE_BF16, SWS_DTYPE_F16 = 1, 2
+_DTYPE_16 = {torch.bfloat16: SWS_DTYPE_BF16, torch.float16: SWS_DTYPE_F16}
+
+
+def sws_slide1d_16(op, x, w, scale=1.0, y=None, stream=None):
+    """x [..., len] of bfloat16 or float16 -> y [..., len-w+1] of the same type (fp32 arithmetic)."""
+    if not isinstance(x, torch.Tensor) or not x.is_cuda:
+        raise TypeError("x must be a GPU tensor")
+    if x.dtype not in _DTYPE_16 or not x.is_contiguous():
+        raise TypeError("x must be contiguous bfloat16 or float16")
+    length = x.shape[-1]
+    rows = x.numel() // length if length else 0
+    lo = length - w + 1
+    if lo < 1 or w < 1:
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_slide1d_16")
+    shape = tuple(x.shape[:-1]) + (lo,)
+    if y is None:
+        y = torch.empty(shape, dtype=x.dtype, device=x.device)
+    elif (not isinstance(y, torch.Tensor) or not y.is_cuda or y.dtype != x.dtype or not y.is_contiguous()
+          or tuple(y.shape) != shape):
+        raise TypeError("y must be a contiguous GPU tensor of x's type and shape %s" % (shape,))
+    _check(lib().sws_slide1d_16(op, _DTYPE_16[x.dtype], x.data_ptr(), y.data_ptr(), rows, length, w, scale,
+                                _stream(stream)), "sws_slide1d_16")
     return y
 
 

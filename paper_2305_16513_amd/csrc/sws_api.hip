@@ -85,6 +85,19 @@ sws_status sws_slide1d(sws_op op, const float *x, float *y, int64_t rows, int64_
     return from_hip(sws::launch_slide1d((int)op, x, y, rows, len, w, 0, 0, SWS_PAD_IDENTITY, scale, (hipStream_t)stream));
 }
 
+sws_status sws_slide1d_16(sws_op op, sws_dtype dtype, const void *x, void *y, int64_t rows, int64_t len, int32_t w,
+                          float scale, void *stream)
+{
+    if (!valid_op((int)op) || rows < 0 || len < 0 || w < 1) return SWS_ERR_INVALID_ARG;
+    if (dtype != SWS_DTYPE_BF16 && dtype != SWS_DTYPE_F16) return SWS_ERR_INVALID_ARG;
+    if (len > kMaxDim || (int64_t)w > len) return SWS_ERR_INVALID_ARG;
+    int64_t n_in;
+    if (!mul3(rows, len, 1, &n_in)) return SWS_ERR_INVALID_ARG;
+    if (rows == 0) return SWS_OK;
+    if (!x || !y) return SWS_ERR_INVALID_ARG;
+    return from_hip(sws::launch_slide1d_16((int)op, (int)dtype, x, y, rows, len, w, scale, (hipStream_t)stream));
+}
+
 sws_status sws_slide1d_padded(sws_op op, const float *x, float *y, int64_t rows, int64_t len, int32_t w,
                               int32_t pad_left, int32_t pad_right, sws_pad_mode mode, float scale, void *stream)
 {

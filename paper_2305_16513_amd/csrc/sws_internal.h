@@ -71,6 +71,8 @@ inline int64_t xcd_grid(int64_t n_units) { return ((n_units + kXcd - 1) / kXcd) 
 hipError_t launch_copy(const float *src, float *dst, int64_t n, hipStream_t s);
 hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_t len, int32_t w,
                           int32_t pad_left, int32_t pad_right, int pad_mode, float scale, hipStream_t s);
+hipError_t launch_slide1d_16(int op, int dtype, const void *x, void *y, int64_t rows, int64_t len, int32_t w,
+                             float scale, hipStream_t s);
 // Generic-operator kernels (slide_generic.hip): the pair operator, and +, max, min as a cross-check.
 hipError_t launch_slide1d_pair(const float *u, const float *v, float *yu, float *yv, int64_t rows, int64_t len,
                                int32_t w, hipStream_t s);

@@ -663,3 +663,45 @@ def test_adjoint_of_dense_convolution_swaps_channels_and_flips_taps():
     wt2 = np.ascontiguousarray(w2.transpose(1, 0, 2, 3)[:, :, ::-1, ::-1])
     gx2, _ = oracle.conv2d(g2, wt2, 1, 1, 1, 1)
     assert abs(float((y2 * g2).sum()) - float((x2.astype(np.float64) * gx2).sum())) < 1e-10
+
+
+# ----------------------------------------------------------------------------- P12
+# round16: the nearest bf16 / fp16 value, ties to even — how a result on 16-bit storage is written.
+def test_round16_hand_written_ties_subnormals_and_overflow():
+    bf = oracle.round16(np.array([1 + 2.0**-8, 1 + 2.0**-7 + 2.0**-8, 1 + 2.0**-8 + 2.0**-40, -(1 + 2.0**-8),
+                                  0.0, 3.0, 2.0**-133 * 1.5, 2.0**-134, 3.39e38, 3.4e38]), oracle.DTYPE_BF16)
+    want = [1.0, 1 + 2.0**-6, 1 + 2.0**-7, -1.0, 0.0, 3.0, 2.0**-132, 0.0, (2 - 2.0**-7) * 2.0**127, np.inf]
+    assert bf.tolist() == want
+    h = oracle.round16(np.array([1 + 2.0**-11, 1 + 2.0**-10 + 2.0**-11, 2049.0, 2051.0, 65504.0, 65519.99, 65520.0,
+                                 2.0**-25, 2.0**-25 * 1.01, 2.0**-24 * 2.5, -2.0**-24 * 3.5]), oracle.DTYPE_F16)
+    want = [1.0, 1 + 2.0**-9, 2048.0, 2052.0, 65504.0, 65504.0, np.inf, 0.0, 2.0**-24, 2.0**-23, -2.0**-22]
+    assert h.tolist() == want
+
+
+def test_round16_matches_the_library_casts():
+    """fp16 against numpy's double -> float16 cast; bf16 against torch's float32 -> bfloat16 cast (on values
+    that are float32 already, so that cast rounds once)."""
+    import torch
+    r = _rng(140)
+    v = np.concatenate([r.standard_normal(20000) * 10.0 ** r.integers(-9, 5, 20000),
+                        np.ldexp(r.integers(0, 4096, 4000) + 0.5, r.integers(-30, 4, 4000)),      # exact ties
+                        np.array([0.0, -0.0, 65504.0, 65519.0, 65521.0, 1e6])])
+    with np.errstate(over="ignore"):
+        want = v.astype(np.float16).astype(np.float64)
+    got = oracle.round16(v, oracle.DTYPE_F16)
+    assert np.array_equal(got, want)
+    v32 = np.concatenate([v.astype(np.float32), np.ldexp(r.integers(128, 256, 4000) + 0.5, r.integers(-140, 120, 4000))
+                          .astype(np.float32)])
+    want_bf = torch.from_numpy(v32).to(torch.bfloat16).to(torch.float64).numpy()
+    got_bf = oracle.round16(v32.astype(np.float64), oracle.DTYPE_BF16)
+    assert np.array_equal(got_bf, want_bf)
+
+
+def test_round16_is_idempotent_monotone_and_within_half_a_step():
+    r = _rng(141)
+    v = np.sort(r.standard_normal(5000) * 100)
+    for dt, frac in ((oracle.DTYPE_BF16, 7), (oracle.DTYPE_F16, 10)):
+        q = oracle.round16(v, dt)
+        assert np.array_equal(oracle.round16(q, dt), q)
+        assert (np.diff(q) >= 0).all()
+        assert (np.abs(q - v) <= np.abs(v) * 2.0 ** -(frac + 1)).all()
