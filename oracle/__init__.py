@@ -14,6 +14,8 @@ from .ref import (  # noqa: F401
     OP_MIN,
     build,
     conv1d,
+    conv1d_grad_input,
+    conv1d_grad_weight,
     conv2d,
     pool2d,
     round16,

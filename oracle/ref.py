@@ -50,6 +50,9 @@ def _load():
                                                ctypes.c_int, _f64]
         lib.sws_ref_slide1d_pair.restype = ctypes.c_int
         lib.sws_ref_slide1d_pair.argtypes = [_fp, _fp, _dp, _dp, _dp, _dp, _i64, _i64, _i32]
+        for f in (lib.sws_ref_conv1d_grad_input, lib.sws_ref_conv1d_grad_weight):
+            f.restype = ctypes.c_int
+            f.argtypes = [_fp, _fp, _dp, _dp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32]
         lib.sws_ref_round16.restype = ctypes.c_int
         lib.sws_ref_round16.argtypes = [_dp, _dp, _i64, ctypes.c_int]
         lib.sws_ref_conv1d.restype = ctypes.c_int
@@ -207,3 +210,40 @@ def conv2d(x, wgt, sh=1, sw=1, ph=0, pw=0):
     if rc:
         raise ValueError("sws_ref_conv2d rejected its arguments")
     return y, s
+
+
+def conv1d_grad_input(gy, wgt, length, stride=1, pad=0, dilation=1, groups=1):
+    """gy: [B, Cout, Lo], wgt: [Cout, Cin/groups, k] float32, length = L of the forward input
+    -> (gx, abs_sum) [B, Cin, L] float64: the adjoint of conv1d with respect to x."""
+    gy = _f32(gy)
+    wgt = _f32(wgt)
+    b, cout, lo = gy.shape
+    cout2, cig, k = wgt.shape
+    cin = cig * groups
+    if cout2 != cout or lo != (length + 2 * pad - dilation * (k - 1) - 1) // stride + 1:
+        raise ValueError("gy does not have the forward output's shape")
+    gx = np.empty((b, cin, length), np.float64)
+    s = np.empty((b, cin, length), np.float64)
+    rc = _load().sws_ref_conv1d_grad_input(_ptr_f(gy), _ptr_f(wgt), _ptr_d(gx), _ptr_d(s), b, cin, length, cout,
+                                           k, stride, pad, dilation, groups)
+    if rc:
+        raise ValueError("sws_ref_conv1d_grad_input rejected its arguments")
+    return gx, s
+
+
+def conv1d_grad_weight(x, gy, k, stride=1, pad=0, dilation=1, groups=1):
+    """x: [B, Cin, L], gy: [B, Cout, Lo] float32 -> (gw, abs_sum) [Cout, Cin/groups, k] float64:
+    the adjoint of conv1d with respect to wgt."""
+    x = _f32(x)
+    gy = _f32(gy)
+    b, cin, length = x.shape
+    b2, cout, lo = gy.shape
+    if b2 != b or lo != (length + 2 * pad - dilation * (k - 1) - 1) // stride + 1:
+        raise ValueError("gy does not have the forward output's shape")
+    gw = np.empty((cout, cin // groups, k), np.float64)
+    s = np.empty((cout, cin // groups, k), np.float64)
+    rc = _load().sws_ref_conv1d_grad_weight(_ptr_f(x), _ptr_f(gy), _ptr_d(gw), _ptr_d(s), b, cin, length, cout,
+                                            k, stride, pad, dilation, groups)
+    if rc:
+        raise ValueError("sws_ref_conv1d_grad_weight rejected its arguments")
+    return gw, s

@@ -26,6 +26,11 @@
  *   sws_ref_slide1d_pair  Eq. 3 with the pair operator of Section 2.4, Eq. 8:
  *                    (u_i, v_i) (+) (u_j, v_j) = (u_i*u_j, u_j*v_i + v_j), i older.
  *                    Non-commutative; folded strictly left to right.
+ *   sws_ref_conv1d_grad_input / _grad_weight  the two adjoints of sws_ref_conv1d (the training
+ *                    side of Section 2.5's sliding dot product), written as SCATTER loops over
+ *                    the forward sum's terms: every term wgt*x of output (b,co,i) sends
+ *                    wgt*gy to gx at x's index and x*gy to gw at wgt's index.  The GPU
+ *                    gathers instead (flipped taps, swapped channels; a reduction).
  *   sws_ref_round16  the value of the bf16 / fp16 number nearest to a double (ties to the even
  *                    significand, overflow to infinity): how a result computed on 16-bit
  *                    storage (the quantised inputs the paper's introduction mentions) is
@@ -53,7 +58,10 @@
  * hand-folded case, u = 1 (sliding add of v), v = 0 (sliding product of u),
  * exact rational arithmetic on small integers, order sensitivity, and the
  * Eq. 7 sequence whose full-length window yields the dot product; for round16 the
- * library's own fp16 / bf16 casts, hand-written ties, subnormals and overflow.
+ * library's own fp16 / bf16 casts, hand-written ties, subnormals and overflow; for the
+ * adjoints the inner-product identities <conv(x;W), g> = <x, gx> = <W, gw> against the pinned
+ * forward function, one-hot cases written out by hand, and central differences of the
+ * (bilinear, hence exactly differentiated) loss <conv(x;W), g>.
  */
 #include <math.h>
 #include <stddef.h>
@@ -339,5 +347,81 @@ int sws_ref_round16(const double *in, double *out, int64_t n, int dtype)
     for (int64_t i = 0; i < n; ++i)
         out[i] = dtype == 1 ? round_to_format(in[i], 7, -126, ldexp(2.0 - ldexp(1.0, -7), 127))
                             : round_to_format(in[i], 10, -14, 65504.0);
+    return 0;
+}
+
+/* Adjoint of sws_ref_conv1d with respect to x: gx[b,ci,j] = sum of wgt[co,ci,t] * gy[b,co,i]
+ * over every (co, i, t) whose forward term reads x[b,ci,j], i.e. j = i*stride + t*dilation - pad.
+ * Scatter form; one image per thread so that no two threads write the same gx.
+ * abs_sum (optional) receives sum|terms| per gx element. */
+int sws_ref_conv1d_grad_input(const float *gy, const float *wgt, double *gx, double *abs_sum,
+                              int64_t B, int64_t Cin, int64_t L, int64_t Cout,
+                              int32_t k, int32_t stride, int32_t pad, int32_t dilation, int32_t groups)
+{
+    if (B < 0 || Cin < 1 || L < 0 || Cout < 1 || k < 1 || stride < 1 || pad < 0 || dilation < 1 || groups < 1) return 1;
+    if (Cin % groups || Cout % groups) return 1;
+    const int64_t span = (int64_t)dilation * (k - 1) + 1;
+    if (span > L + 2 * (int64_t)pad) return 1;
+    const int64_t Lo = (L + 2 * (int64_t)pad - span) / stride + 1;
+    const int64_t cig = Cin / groups, cog = Cout / groups;
+    if (B > 0 && (!gy || !wgt || !gx)) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t b = 0; b < B; ++b) {
+        for (int64_t e = 0; e < Cin * L; ++e) {
+            gx[b * Cin * L + e] = 0.0;
+            if (abs_sum) abs_sum[b * Cin * L + e] = 0.0;
+        }
+        for (int64_t co = 0; co < Cout; ++co) {
+            const int64_t g = co / cog;
+            for (int64_t i = 0; i < Lo; ++i) {
+                const double gyv = (double)gy[(b * Cout + co) * Lo + i];
+                for (int64_t ci = 0; ci < cig; ++ci)
+                    for (int32_t t = 0; t < k; ++t) {
+                        const int64_t j = i * stride + (int64_t)t * dilation - pad;
+                        if (j < 0 || j >= L) continue;
+                        const double term = (double)wgt[(co * cig + ci) * k + t] * gyv;
+                        const int64_t at = (b * Cin + g * cig + ci) * L + j;
+                        gx[at] += term;
+                        if (abs_sum) abs_sum[at] += fabs(term);
+                    }
+            }
+        }
+    }
+    return 0;
+}
+
+/* Adjoint with respect to wgt: gw[co,ci,t] = sum over (b, i) of x[b, g*cig+ci, i*stride + t*dilation - pad]
+ * * gy[b,co,i] (terms in the padding are absent).  Scatter form; one output channel per thread. */
+int sws_ref_conv1d_grad_weight(const float *x, const float *gy, double *gw, double *abs_sum,
+                               int64_t B, int64_t Cin, int64_t L, int64_t Cout,
+                               int32_t k, int32_t stride, int32_t pad, int32_t dilation, int32_t groups)
+{
+    if (B < 0 || Cin < 1 || L < 0 || Cout < 1 || k < 1 || stride < 1 || pad < 0 || dilation < 1 || groups < 1) return 1;
+    if (Cin % groups || Cout % groups) return 1;
+    const int64_t span = (int64_t)dilation * (k - 1) + 1;
+    if (span > L + 2 * (int64_t)pad) return 1;
+    const int64_t Lo = (L + 2 * (int64_t)pad - span) / stride + 1;
+    const int64_t cig = Cin / groups, cog = Cout / groups;
+    if (!gw || (B > 0 && (!x || !gy))) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t co = 0; co < Cout; ++co) {
+        const int64_t g = co / cog;
+        for (int64_t e = 0; e < cig * k; ++e) {
+            gw[co * cig * k + e] = 0.0;
+            if (abs_sum) abs_sum[co * cig * k + e] = 0.0;
+        }
+        for (int64_t b = 0; b < B; ++b)
+            for (int64_t i = 0; i < Lo; ++i) {
+                const double gyv = (double)gy[(b * Cout + co) * Lo + i];
+                for (int64_t ci = 0; ci < cig; ++ci)
+                    for (int32_t t = 0; t < k; ++t) {
+                        const int64_t j = i * stride + (int64_t)t * dilation - pad;
+                        if (j < 0 || j >= L) continue;
+                        const double term = (double)x[(b * Cin + g * cig + ci) * L + j] * gyv;
+                        gw[(co * cig + ci) * k + t] += term;
+                        if (abs_sum) abs_sum[(co * cig + ci) * k + t] += fabs(term);
+                    }
+            }
+    }
     return 0;
 }

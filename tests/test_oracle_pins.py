@@ -705,3 +705,87 @@ def test_round16_is_idempotent_monotone_and_within_half_a_step():
         assert np.array_equal(oracle.round16(q, dt), q)
         assert (np.diff(q) >= 0).all()
         assert (np.abs(q - v) <= np.abs(v) * 2.0 ** -(frac + 1)).all()
+
+
+# ----------------------------------------------------------------------------- P13
+# The adjoints of the sliding dot product (scatter form) against the pinned forward function.
+GRAD_CASES = [  # B, Cin, L, Cout, k, stride, pad, dilation, groups
+    (2, 3, 41, 3, 5, 1, 2, 1, 3), (2, 4, 37, 6, 3, 1, 1, 1, 1), (1, 4, 50, 8, 4, 2, 3, 1, 2),
+    (3, 2, 33, 2, 3, 1, 0, 4, 2), (2, 6, 29, 4, 2, 3, 1, 2, 2), (1, 1, 20, 1, 20, 1, 0, 1, 1)]
+
+
+@pytest.mark.parametrize("case", GRAD_CASES)
+def test_conv1d_adjoints_satisfy_the_inner_product_identities(case):
+    b, cin, length, cout, k, stride, pad, dil, groups = case
+    r = _rng(150 + k + cin)
+    x = r.standard_normal((b, cin, length), dtype=np.float32)
+    w = r.standard_normal((cout, cin // groups, k), dtype=np.float32)
+    y, _ = oracle.conv1d(x, w, stride, pad, dil, groups)
+    g = r.standard_normal(y.shape).astype(np.float32)
+    gx, _ = oracle.conv1d_grad_input(g, w, length, stride, pad, dil, groups)
+    gw, _ = oracle.conv1d_grad_weight(x, g, k, stride, pad, dil, groups)
+    loss = float((y * g).sum())
+    assert gx.shape == x.shape and gw.shape == w.shape
+    assert abs(loss - float((x.astype(np.float64) * gx).sum())) < 1e-9 * max(1.0, abs(loss))
+    assert abs(loss - float((w.astype(np.float64) * gw).sum())) < 1e-9 * max(1.0, abs(loss))
+
+
+def test_conv1d_adjoints_are_the_derivatives_of_the_bilinear_loss():
+    """loss(x, W) = <conv(x; W), g> is linear in x and in W: a central difference is its exact
+    partial derivative (up to fp64 rounding), element by element."""
+    b, cin, length, cout, k, stride, pad, dil, groups = 1, 4, 19, 4, 3, 2, 2, 2, 2
+    r = _rng(160)
+    x = r.integers(-3, 4, (b, cin, length)).astype(np.float32)
+    w = r.integers(-3, 4, (cout, cin // groups, k)).astype(np.float32)
+    y, _ = oracle.conv1d(x, w, stride, pad, dil, groups)
+    g = r.integers(-3, 4, y.shape).astype(np.float32)
+    gx, _ = oracle.conv1d_grad_input(g, w, length, stride, pad, dil, groups)
+    gw, _ = oracle.conv1d_grad_weight(x, g, k, stride, pad, dil, groups)
+    loss = lambda xx, ww: float((oracle.conv1d(xx, ww, stride, pad, dil, groups)[0] * g).sum())
+    for idx in np.ndindex(x.shape):
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += 1
+        xm[idx] -= 1
+        assert (loss(xp, w) - loss(xm, w)) / 2 == gx[idx]
+    for idx in np.ndindex(w.shape):
+        wp, wm = w.copy(), w.copy()
+        wp[idx] += 1
+        wm[idx] -= 1
+        assert (loss(x, wp) - loss(x, wm)) / 2 == gw[idx]
+
+
+def test_conv1d_adjoints_hand_written_one_hot_cases():
+    """One output gradient at i = 2 (k = 3, pad 1, stride 1): it returns the taps to x[1..3] and
+    x[1..3] to the taps; at i = 0 the first tap fell into the padding and gets nothing."""
+    x = np.array([[[1, 2, 3, 4, 5]]], np.float32)
+    w = np.array([[[10, 20, 30]]], np.float32)
+    g = np.zeros((1, 1, 5), np.float32)
+    g[0, 0, 2] = 2
+    gx, mag = oracle.conv1d_grad_input(g, w, 5, 1, 1, 1, 1)
+    assert gx.ravel().tolist() == [0, 20, 40, 60, 0] and mag.ravel().tolist() == [0, 20, 40, 60, 0]
+    gw, _ = oracle.conv1d_grad_weight(x, g, 3, 1, 1, 1, 1)
+    assert gw.ravel().tolist() == [4, 6, 8]
+    g[:] = 0
+    g[0, 0, 0] = 1
+    gw, _ = oracle.conv1d_grad_weight(x, g, 3, 1, 1, 1, 1)
+    assert gw.ravel().tolist() == [0, 1, 2]
+    gx, _ = oracle.conv1d_grad_input(g, w, 5, 1, 1, 1, 1)
+    assert gx.ravel().tolist() == [20, 30, 0, 0, 0]
+    # stride 2, dilation 2, no padding: output 1 reads x[2], x[4], x[6]
+    g2 = np.array([[[0, 1]]], np.float32)
+    gx, _ = oracle.conv1d_grad_input(g2, w, 7, 2, 0, 2, 1)
+    assert gx.ravel().tolist() == [0, 0, 10, 0, 20, 0, 30]
+
+
+def test_conv1d_grad_input_is_the_forward_function_on_flipped_taps_at_stride_one():
+    """The gather form the GPU uses: taps flipped, channels swapped inside each group, padding span - pad."""
+    b, cin, length, cout, k, pad, dil, groups = 2, 4, 31, 6, 4, 2, 3, 2
+    r = _rng(170)
+    w = r.standard_normal((cout, cin // groups, k), dtype=np.float32)
+    lo = length + 2 * pad - dil * (k - 1)
+    g = r.standard_normal((b, cout, lo), dtype=np.float32)
+    gx, _ = oracle.conv1d_grad_input(g, w, length, 1, pad, dil, groups)
+    cig, cog = cin // groups, cout // groups
+    wt = np.ascontiguousarray(w.reshape(groups, cog, cig, k).transpose(0, 2, 1, 3)[..., ::-1]).reshape(cin, cog, k)
+    via, _ = oracle.conv1d(g, wt, 1, dil * (k - 1) - pad, dil, groups)
+    assert np.abs(via - gx).max() < 1e-12
