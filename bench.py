@@ -183,7 +183,7 @@ def sweeps_table(torch, B, workloads, iters=20):
     2*k FLOP per output; the vector-ALU peak without packed fp32 is 78.6 TFLOP/s."""
     g = lambda a: torch.from_numpy(a).cuda()
     out = {"filter_sweep": {}, "dilated_single": {}, "dilated_batched": {}, "pair_operator": {}, "same_size_pooling": {},
-           "storage_16bit": {}}
+           "storage_16bit": {}, "adjoints": {}}
     c6 = workloads.CONFIGS[6]
     rows, length = c6.x_shape[0], c6.x_shape[2]
     x6 = g(workloads.make(6)[0])
@@ -271,6 +271,45 @@ def sweeps_table(torch, B, workloads, iters=20):
         del xs
     del x16
     torch.cuda.empty_cache()
+    # the adjoints of the sliding dot product (training): configuration 5's depthwise layer (HBM-bound:
+    # grad-input moves what the forward pass moves, grad-weight reads x and gy) and configuration 2's
+    # dense layer (matrix cores; 2*Cin*k FLOP per output element for either adjoint)
+    x5, t5 = workloads.make(5)
+    x5, t5 = g(x5), g(t5)
+    lo = LEN5 - K5 + 1
+    gy5 = torch.empty(256, 128, lo, device="cuda").uniform_(-1, 1)
+    gx5 = torch.empty_like(x5)
+    gw5 = torch.empty_like(t5)
+    nb, fl = slide_bytes(ROWS5, LEN5, K5) + 4 * CH5 * K5, 2.0 * ROWS5 * lo * K5
+    for name, fn in (("dwconv_k31_grad_input", lambda: B.sws_conv1d_grad_input(gy5, t5, LEN5, groups=CH5, gx=gx5)),
+                     ("dwconv_k31_grad_weight", lambda: B.sws_conv1d_grad_weight(x5, gy5, K5, groups=CH5, gw=gw5))):
+        ms = time_launches(torch, fn, iters)
+        out["adjoints"][name] = {"ms": round(ms, 4), "GBps": round(nb / ms / 1e6, 1),
+                                 "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4), "TFLOPs": round(fl / ms / 1e9, 2)}
+    del x5, gy5, gx5
+    torch.cuda.empty_cache()
+    x2, w2 = workloads.make(2)
+    x2, w2 = g(x2), g(w2)
+    gy2 = torch.empty(16, 64, 4094, device="cuda").normal_()
+    gx2, gw2 = torch.empty_like(x2), torch.empty_like(w2)
+    fl = 2.0 * 16 * 64 * 4094 * 64 * 3
+    for name, fn in (("cfg2_conv1d_grad_input", lambda: B.sws_conv1d_grad_input(gy2, w2, 4096, gx=gx2)),
+                     ("cfg2_conv1d_grad_weight", lambda: B.sws_conv1d_grad_weight(x2, gy2, 3, gw=gw2))):
+        ms = time_launches(torch, fn, iters)
+        out["adjoints"][name] = {"us": round(ms * 1e3, 2), "TFLOPs": round(fl / ms / 1e9, 2),
+                                 "frac_fp32_mfma_peak": round(fl / ms / 1e9 / 157.3, 4)}
+    xr = torch.empty(32, 256, 3136, device="cuda").normal_()
+    gr = torch.empty(32, 256, 3136, device="cuda").normal_()
+    wr = torch.empty(256, 256, 3, device="cuda").normal_()
+    gxr, gwr = torch.empty_like(xr), torch.empty_like(wr)
+    fl = 2.0 * 32 * 3136 * 256 * 256 * 3
+    for name, fn in (("dense_256x256_k3_b32_l3136_grad_input", lambda: B.sws_conv1d_grad_input(gr, wr, 3136, 1, 1, gx=gxr)),
+                     ("dense_256x256_k3_b32_l3136_grad_weight", lambda: B.sws_conv1d_grad_weight(xr, gr, 3, 1, 1, gw=gwr))):
+        ms = time_launches(torch, fn, iters)
+        out["adjoints"][name] = {"ms": round(ms, 4), "TFLOPs": round(fl / ms / 1e9, 2),
+                                 "frac_fp32_mfma_peak": round(fl / ms / 1e9 / 157.3, 4)}
+    del xr, gr, gxr
+    torch.cuda.empty_cache()
     return out
 
 
@@ -281,6 +320,26 @@ def run_only(torch, B, workloads, name, steps):
         src = torch.rand(ROWS5, LEN5, device="cuda")
         dst = torch.empty_like(src)
         fn = lambda: B.sws_copy(src, dst)
+    elif name in ("grad_input_dwconv_k31", "grad_weight_dwconv_k31"):
+        x, taps = workloads.make(5)
+        x, taps = g(x), g(taps)
+        gy = torch.empty(256, 128, LEN5 - K5 + 1, device="cuda").uniform_(-1, 1)
+        if name.startswith("grad_input"):
+            gx = torch.empty_like(x)
+            fn = lambda: B.sws_conv1d_grad_input(gy, taps, LEN5, groups=CH5, gx=gx)
+        else:
+            gw = torch.empty_like(taps)
+            fn = lambda: B.sws_conv1d_grad_weight(x, gy, K5, groups=CH5, gw=gw)
+    elif name in ("grad_input_cfg2", "grad_weight_cfg2"):
+        x2, w2 = workloads.make(2)
+        x2, w2 = g(x2), g(w2)
+        gy = torch.empty(16, 64, 4094, device="cuda").normal_()
+        if name.startswith("grad_input"):
+            gx = torch.empty_like(x2)
+            fn = lambda: B.sws_conv1d_grad_input(gy, w2, 4096, gx=gx)
+        else:
+            gw = torch.empty_like(w2)
+            fn = lambda: B.sws_conv1d_grad_weight(x2, gy, 3, gw=gw)
     elif name.startswith("slide16_"):                     # slide16_<bf16|f16>_<add|max>_w<w>
         _, dn, opn, wn = name.split("_")
         w = int(wn[1:])

@@ -142,6 +142,27 @@ sws_status sws_conv1d(const float *x, const float *wgt, float *y, int64_t B, int
                       int64_t L, int64_t Cout, int32_t k, int32_t stride, int32_t pad,
                       int32_t dilation, int32_t groups, void *stream);
 
+/* The two adjoints of sws_conv1d (the training side of the sliding dot product of Section 2.5;
+ * the abstract names training next to inference).  With loss = sum(gy * y):
+ *
+ *   gx[b,c,j]     = sum over (co, t) of the group of c with j + pad - t*dilation = i*stride,
+ *                   0 <= i < Lo:   wgt[co, ci, t] * gy[b, co, i]                (d loss / d x)
+ *   gw[co,ci,t]   = sum over (b, i) with 0 <= i*stride + t*dilation - pad < L:
+ *                   gy[b, co, i] * x[b, g*Cin/groups + ci, i*stride + t*dilation - pad]
+ *                                                                              (d loss / d wgt)
+ *
+ * All sizes are those of the forward call (L is the length of x, Lo = sws_out_len(...) that of
+ * gy).  gx and gw are overwritten, not accumulated into.  gw is summed with atomic adds whose
+ * order is not fixed: its last bits may differ between runs.
+ *   gy : device [B,Cout,Lo]   wgt, gw : device [Cout,Cin/groups,k]   x, gx : device [B,Cin,L]
+ * Errors: as sws_conv1d. */
+sws_status sws_conv1d_grad_input(const float *gy, const float *wgt, float *gx, int64_t B,
+                                 int64_t Cin, int64_t L, int64_t Cout, int32_t k, int32_t stride,
+                                 int32_t pad, int32_t dilation, int32_t groups, void *stream);
+sws_status sws_conv1d_grad_weight(const float *x, const float *gy, float *gw, int64_t B,
+                                  int64_t Cin, int64_t L, int64_t Cout, int32_t k, int32_t stride,
+                                  int32_t pad, int32_t dilation, int32_t groups, void *stream);
+
 /* 2-D convolution (same reading of Section 2.5 on NCHW x and OIHW wgt, groups = 1):
  *
  *   y[n,co,ho,wo] = sum_ci sum_{a<kh} sum_{b<kw} wgt[co,ci,a,b] * x[n,ci, ho*sh-ph+a, wo*sw-pw+b]

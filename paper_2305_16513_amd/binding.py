@@ -19,7 +19,7 @@ _lib = None
 
 _i64, _i32, _f32, _vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
 
-EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_conv1d", "sws_conv2d", "sws_copy", "sws_out_len",
+EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_conv1d", "sws_conv1d_grad_input", "sws_conv1d_grad_weight", "sws_conv2d", "sws_copy", "sws_out_len",
            "sws_status_string", "sws_set_option", "sws_version")
 
 
@@ -50,6 +50,9 @@ def lib():
                                  _i32, _i32, _i32, _i32, _i32, _i32, _f32, _vp]
         L.sws_conv1d.restype = ctypes.c_int
         L.sws_conv1d.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _vp]
+        for f in (L.sws_conv1d_grad_input, L.sws_conv1d_grad_weight):
+            f.restype = ctypes.c_int
+            f.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _vp]
         L.sws_conv2d.restype = ctypes.c_int
         L.sws_conv2d.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64,
                                  _i32, _i32, _i32, _i32, _i32, _i32, _vp]
@@ -215,6 +218,35 @@ def sws_conv1d(x, wgt, stride=1, pad=0, dilation=1, groups=1, y=None, stream=Non
     _check(lib().sws_conv1d(x.data_ptr(), wgt.data_ptr(), y.data_ptr(), b, cin, length, cout, k, stride,
                             pad, dilation, groups, _stream(stream)), "sws_conv1d")
     return y
+
+
+def sws_conv1d_grad_input(gy, wgt, length, stride=1, pad=0, dilation=1, groups=1, gx=None, stream=None):
+    """gy [B, Cout, Lo], wgt [Cout, Cin/groups, k], length = L of the forward input -> gx [B, Cin, L]."""
+    _dev(gy, "gy")
+    _dev(wgt, "wgt")
+    b, cout, lo = gy.shape
+    cout2, cig, k = wgt.shape
+    if cout2 != cout or lo != sws_out_len(length, k, stride, pad, dilation):
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_conv1d_grad_input")
+    cin = cig * groups
+    gx = _out(gx, (b, cin, length), gy, "gx")
+    _check(lib().sws_conv1d_grad_input(gy.data_ptr(), wgt.data_ptr(), gx.data_ptr(), b, cin, length, cout, k, stride,
+                                       pad, dilation, groups, _stream(stream)), "sws_conv1d_grad_input")
+    return gx
+
+
+def sws_conv1d_grad_weight(x, gy, k, stride=1, pad=0, dilation=1, groups=1, gw=None, stream=None):
+    """x [B, Cin, L], gy [B, Cout, Lo] -> gw [Cout, Cin/groups, k]."""
+    _dev(x, "x")
+    _dev(gy, "gy")
+    b, cin, length = x.shape
+    b2, cout, lo = gy.shape
+    if b2 != b or cin % groups or lo != sws_out_len(length, k, stride, pad, dilation):
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_conv1d_grad_weight")
+    gw = _out(gw, (cout, cin // groups, k), x, "gw")
+    _check(lib().sws_conv1d_grad_weight(x.data_ptr(), gy.data_ptr(), gw.data_ptr(), b, cin, length, cout, k, stride,
+                                        pad, dilation, groups, _stream(stream)), "sws_conv1d_grad_weight")
+    return gw
 
 
 def sws_conv2d(x, wgt, sh=1, sw=1, ph=0, pw=0, y=None, stream=None):

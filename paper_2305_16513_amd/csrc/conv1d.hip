@@ -42,7 +42,8 @@ __host__ __device__ constexpr int lds_pos(int q) { return q + 4 * (q >> 4); }
 template <int KB4>
 __global__ __launch_bounds__(kThreads, (KB4 <= 8 ? 5 : 4)) void conv1d_thin_kernel(
     const float *__restrict__ x, const float *__restrict__ wgt, float *__restrict__ y, int L, int Lo, int k,
-    int pad, int Cin, int Cout, int cog, int tiles_per_row, int group, int chunks_per_row, int64_t n_units)
+    int pad, int Cin, int Cout, int cog, int tiles_per_row, int group, int chunks_per_row, int64_t n_units,
+    int wflip)
 {
     constexpr int K4 = 4 * KB4;                      // taps, zero-padded to a multiple of 4
     constexpr int NI = kTileOut + K4;                // staged inputs per tile
@@ -69,7 +70,7 @@ __global__ __launch_bounds__(kThreads, (KB4 <= 8 ? 5 : 4)) void conv1d_thin_kern
     // Taps: one coalesced load (lane t holds tap t, zero beyond k), then broadcast into scalar registers.
     float f[K4];
     {
-        float tv = wr[lane < k ? lane : 0];
+        float tv = wr[lane < k ? (wflip ? k - 1 - lane : lane) : 0];   // wflip: the adjoint's taps, last first
         tv = lane < k ? tv : 0.0f;
 #pragma unroll
         for (int t = 0; t < K4; ++t) f[t] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(tv), t));
@@ -166,7 +167,7 @@ __global__ __launch_bounds__(kThreads, (KB4 <= 8 ? 5 : 4)) void conv1d_thin_kern
 
 template <int KB4>
 hipError_t launch_thin(const float *x, const float *wgt, float *y, int64_t rows_out, int L, int Lo, int k, int pad,
-                       int Cin, int Cout, int cog, hipStream_t s)
+                       int Cin, int Cout, int cog, hipStream_t s, int wflip)
 {
     const int tiles_per_row = (Lo + 15 + kTileOut - 1) / kTileOut;     // origins move back by up to 15
     // Tiles per workgroup (measured): two per wavefront while HBM is the bound (the tiles in flight
@@ -180,7 +181,7 @@ hipError_t launch_thin(const float *x, const float *wgt, float *y, int64_t rows_
     const int64_t grid = xcd_grid(n_units);
     if (grid > 2147483647LL) return hipErrorInvalidValue;
     hipLaunchKernelGGL((conv1d_thin_kernel<KB4>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, wgt, y, L, Lo, k,
-                       pad, Cin, Cout, cog, tiles_per_row, group, chunks_per_row, n_units);
+                       pad, Cin, Cout, cog, tiles_per_row, group, chunks_per_row, n_units, wflip);
     return hipGetLastError();
 }
 
@@ -201,6 +202,7 @@ constexpr int kDilMaxD = 64;
 struct DilPlan {
     int d, G, MP, slice, TO, NI, tab_strips;
     float inv_d, inv_16d;
+    int wadj;                                        // weights read as the adjoint's (see the kernel)
     int wstride, wofs, accum;                        // a chunk of a longer kernel: taps per channel pair in memory,
                                                      // first tap of this launch, add to what y already holds
 };
@@ -235,7 +237,14 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
     const int64_t b = ro / Cout;
     const int co = (int)(ro - b * Cout);
     const float *xg = x + (b * Cin + (int64_t)(co / cog) * cig) * (int64_t)L;     // first input channel of my group
-    const float *wr = wgt + (int64_t)co * cig * pl.wstride + pl.wofs;
+    // Plain view: wgt[co][ci][wofs + t].  Adjoint view (pl.wadj; this launch maps output gradients
+    // back to the input): my output channel is the stored array's input channel a = co % cog of
+    // group co / cog, my input channel ci its output channel, the taps run backwards:
+    // wgt[(group*cig + ci)][a][wstride - 1 - wofs - t].
+    const int64_t w_sci = pl.wadj ? (int64_t)cog * pl.wstride : pl.wstride;
+    const float *wr = wgt + (pl.wadj ? ((int64_t)(co / cog) * cig * cog + co % cog) * pl.wstride + pl.wstride - 1 - pl.wofs
+                                     : (int64_t)co * cig * pl.wstride + pl.wofs);
+    const int w_st = pl.wadj ? -1 : 1;
     float *yr = y + ro * (int64_t)Lo;
     const int c = (int)((ro * Lo) & 15);             // 64-byte-aligned strip stores, as in the undilated kernel
     const int d = pl.d, MP = pl.MP, TO = pl.TO, NI = pl.NI;
@@ -261,7 +270,7 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_dilated_kernel(
     // Taps: one coalesced load (lane t holds tap t, zero beyond k), then broadcast into scalar registers.
     float f[K4];
     auto load_taps = [&](int ci) {
-        const float tv = wr[ci * pl.wstride + (lane < k ? lane : 0)];
+        const float tv = wr[ci * w_sci + (lane < k ? lane : 0) * w_st];
         return lane < k ? tv : 0.0f;
     };
     auto spread_taps = [&](float tv) {
@@ -424,6 +433,7 @@ bool plan_dilated(int d, int K4, DilPlan *pl)
     pl->inv_16d = 1.0f / (float)(16 * d);
     pl->wstride = 0;
     pl->wofs = 0;
+    pl->wadj = 0;
     pl->accum = 0;
     return pl->slice <= kDilSliceMax;
 }
@@ -454,6 +464,7 @@ bool plan_strided(int s, int K4, DilPlan *pl)
     pl->inv_16d = 0.0f;
     pl->wstride = 0;
     pl->wofs = 0;
+    pl->wadj = 0;
     pl->accum = 0;
     return pl->slice <= kDilSliceMax + 64;
 }
@@ -514,8 +525,12 @@ bool prefer_few(int64_t Cin, int64_t Cout, int k, bool strided)
 
 hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin, int64_t L,
                          int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad, int32_t dilation,
-                         int32_t groups, hipStream_t s)
+                         int32_t groups, hipStream_t s, int wadj, bool *taken)
 {
+    // wadj: wgt is the [Cin, Cout/groups, k] array of the convolution whose adjoint this call
+    // evaluates (x holds output gradients); the kernels read it transposed inside each group, taps
+    // last first.  The direct-evaluation fallback does not know that view: *taken = false then.
+    if (taken) *taken = true;
     int variant = g_opt.conv1d_variant;
     const int cig = (int)(Cin / groups);
     const bool thin_ok = cig == 1 && stride == 1 && dilation == 1 && k <= kThinMaxK;
@@ -531,7 +546,7 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
     // strides (taps adjacent): the same kernel walking the phases of the input
     DilPlan spl;
     const int k_phase = (k + stride - 1) / stride;                 // taps of one phase
-    const bool strided_ok = stride > 1 && dilation == 1 && k <= kThinMaxK && L >= 4 &&
+    const bool strided_ok = !wadj && stride > 1 && dilation == 1 && k <= kThinMaxK && L >= 4 &&
                             plan_strided(stride, 4 * ((k_phase + 3) / 4), &spl);
     if (variant == 2 && !thin_ok) variant = 0;
     if (variant == 4 && !thin_dil_ok) variant = 0;
@@ -547,9 +562,9 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
     }
     if (variant == 3) {
         // the dense contraction is the 2-D kernel on images of height 1
-        bool taken = false;
-        const hipError_t e = launch_conv2d_mfma(x, wgt, y, B, Cin, 1, L, Cout, 1, Lo, 1, k, 1, stride, 0, pad, 1, dilation, s, &taken);
-        if (taken) return e;
+        bool taken_m = false;
+        const hipError_t e = launch_conv2d_mfma(x, wgt, y, B, Cin, 1, L, Cout, 1, Lo, 1, k, 1, stride, 0, pad, 1, dilation, s, &taken_m, wadj);
+        if (taken_m) return e;
         variant = few_ok ? 6 : (strided_ok ? 7 : 1);
     }
     if (variant == 7) {
@@ -571,7 +586,7 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
         const int cog = (int)(Cout / groups);
 #define SWS_THIN(KB)                                                                                            \
     case KB:                                                                                                    \
-        return launch_thin<KB>(x, wgt, y, B * Cout, (int)L, (int)Lo, k, pad, (int)Cin, (int)Cout, cog, s)
+        return launch_thin<KB>(x, wgt, y, B * Cout, (int)L, (int)Lo, k, pad, (int)Cin, (int)Cout, cog, s, wadj)
         switch ((k + 3) / 4) {
             SWS_THIN(1); SWS_THIN(2); SWS_THIN(3); SWS_THIN(4); SWS_THIN(5); SWS_THIN(6); SWS_THIN(7); SWS_THIN(8);
             SWS_THIN(9); SWS_THIN(10); SWS_THIN(11); SWS_THIN(12); SWS_THIN(13); SWS_THIN(14); SWS_THIN(15);
@@ -588,6 +603,7 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
             DilPlan pc = dpl;
             pc.wstride = k;
             pc.wofs = first;
+            pc.wadj = wadj;
             pc.accum = c > 0;
             const int pad_c = pad - first * dilation;           // the chunk's first tap sits first * dilation further on
             hipError_t e = hipErrorInvalidValue;
@@ -605,6 +621,10 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
 #undef SWS_THIN_DIL
             if (e != hipSuccess) return e;
         }
+        return hipSuccess;
+    }
+    if (wadj) {
+        *taken = false;
         return hipSuccess;
     }
     return launch_conv1d_naive(x, wgt, y, B, Cin, L, Cout, Lo, k, stride, pad, dilation, groups, s);

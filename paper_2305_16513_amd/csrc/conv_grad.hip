@@ -1,0 +1,463 @@
+// Adjoints of sws_conv1d (the training side of Section 2.5's sliding dot product).
+//
+//  * with respect to the input: at stride 1 the adjoint is itself a sliding dot product — over
+//    the output gradients, taps last first, channels swapped inside each group, padding
+//    span - 1 - pad — so it runs on the forward kernels, which read the weight array through
+//    that view (no transformed copy is made).  Other cases: one thread per input element.
+//
+//  * with respect to the weights: gw[co,ci,t] = sum over images and positions of
+//    gy[b,co,i] * x[b,ci,i*stride + t*dilation - pad], a reduction over everything the forward
+//    pass slides over.  Two tuned kernels (stride 1):
+//      - thin (one input channel per output channel): a wavefront stages a tile of x and of gy
+//        in LDS, a lane keeps 16 gradients and its window of x in registers and adds
+//        gy[e] * x[e+t] into one accumulator per tap; tiles of the same channel follow each other,
+//        so the cross-lane reduction happens once per workgroup, then one atomic add per tap.
+//      - dense channels: per tap the product GY[co, positions] * X[ci, positions + t*d]^T on the
+//        fp32 matrix cores (positions are the contraction index, split over workgroups and over
+//        the wavefronts of a workgroup), partial blocks added through LDS, then atomic adds.
+//    gw is cleared by a fill kernel first.  The order of the atomic adds is not fixed, so the
+//    last bits of gw can differ from run to run; every other case: one workgroup per element.
+#include "sws_internal.h"
+
+namespace sws {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWavesPerWg = kThreads / kWave;
+constexpr int kTileOut = 1024;
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__global__ __launch_bounds__(kThreads) void fill_zero_kernel(float *__restrict__ p, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kThreads) p[i] = 0.0f;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Direct evaluation.
+// ---------------------------------------------------------------------------------------------
+// gx[b, cin, j] = sum over co in the group and taps t with (j + pad - t*dilation) = i*stride,
+// 0 <= i < Lo, of wgt[co, ci, t] * gy[b, co, i].
+__global__ __launch_bounds__(kThreads) void conv1d_grad_input_naive_kernel(
+    const float *__restrict__ gy, const float *__restrict__ wgt, float *__restrict__ gx, int64_t B, int Cin, int L,
+    int Cout, int Lo, int k, int stride, int pad, int dilation, int groups)
+{
+    const int cig = Cin / groups, cog = Cout / groups;
+    const int64_t total = B * (int64_t)Cin * L;
+    for (int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x; o < total; o += (int64_t)gridDim.x * kThreads) {
+        const int j = (int)(o % L);
+        const int c = (int)((o / L) % Cin);
+        const int64_t b = o / ((int64_t)L * Cin);
+        const int g = c / cig, ci = c - g * cig;
+        float acc = 0.0f;
+        for (int a = 0; a < cog; ++a) {
+            const int co = g * cog + a;
+            const float *gr = gy + (b * Cout + co) * (int64_t)Lo;
+            const float *wr = wgt + ((int64_t)co * cig + ci) * k;
+            for (int t = 0; t < k; ++t) {
+                const int num = j + pad - t * dilation;
+                if (num < 0 || num % stride) continue;
+                const int i = num / stride;
+                if (i < Lo) acc += wr[t] * gr[i];
+            }
+        }
+        gx[o] = acc;
+    }
+}
+
+// One workgroup per gw element: threads stride over (image, position), then a tree in LDS.
+__global__ __launch_bounds__(kThreads) void conv1d_grad_weight_naive_kernel(
+    const float *__restrict__ x, const float *__restrict__ gy, float *__restrict__ gw, int64_t B, int Cin, int L,
+    int Cout, int Lo, int k, int stride, int pad, int dilation, int groups)
+{
+    __shared__ float part[kThreads];
+    const int cig = Cin / groups, cog = Cout / groups;
+    const int64_t e = blockIdx.x;                    // (co * cig + ci) * k + t
+    const int t = (int)(e % k);
+    const int ci = (int)((e / k) % cig);
+    const int co = (int)(e / ((int64_t)k * cig));
+    const int c = (co / cog) * cig + ci;
+    float acc = 0.0f;
+    const int64_t n = B * (int64_t)Lo;
+    for (int64_t o = threadIdx.x; o < n; o += kThreads) {
+        const int64_t b = o / Lo;
+        const int i = (int)(o - b * Lo);
+        const int j = i * stride + t * dilation - pad;
+        if (j >= 0 && j < L) acc += gy[(b * Cout + co) * (int64_t)Lo + i] * x[(b * Cin + c) * (int64_t)L + j];
+    }
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int h = kThreads / 2; h > 0; h >>= 1) {
+        if ((int)threadIdx.x < h) part[threadIdx.x] += part[threadIdx.x + h];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) gw[e] = part[0];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Thin channels (one input channel per output channel), stride 1, taps adjacent, k <= 64.
+// ---------------------------------------------------------------------------------------------
+// LDS layout of a staged tile: element q at q + 4*(q >> 4), so that a lane's window (from 16*lane)
+// starts 20 floats after its neighbour's and the 128-bit reads of eight lanes hit eight bank quads.
+__host__ __device__ constexpr int gpos(int q) { return q + 4 * (q >> 4); }
+
+// Strips of 256 elements of row `src` (valid indices [0, n)) from index p0 on -> LDS, zero outside.
+template <int STRIPS>
+__device__ __forceinline__ void stage_row(float *dst, const float *__restrict__ src, int p0, int n, int lane)
+{
+    v4f g4[STRIPS];
+#pragma unroll
+    for (int j = 0; j < STRIPS; ++j) {
+        const int s0 = p0 + 256 * j;                 // wave-uniform
+        const int q = s0 + 4 * lane;
+        if (s0 >= 0 && s0 + 256 <= n) {
+            g4[j] = *(const v4f_u *)(src + q);
+        } else if (s0 >= n || s0 + 256 <= 0) {
+            g4[j] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+        } else {
+            float e4[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) e4[c] = (q + c >= 0 && q + c < n) ? src[q + c] : 0.0f;
+            g4[j] = (v4f){e4[0], e4[1], e4[2], e4[3]};
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < STRIPS; ++j) *(v4f *)(dst + gpos(256 * j + 4 * lane)) = g4[j];
+}
+
+template <int KB4>
+__global__ __launch_bounds__(kThreads) void conv1d_thin_grad_weight_kernel(
+    const float *__restrict__ x, const float *__restrict__ gy, float *__restrict__ gw, int B, int Cin, int L,
+    int Cout, int Lo, int k, int pad, int cog, int tiles_per_row, int bgroup, int64_t n_units)
+{
+    constexpr int K4 = 4 * KB4;
+    constexpr int XS = (kTileOut + K4 + 255) / 256;  // strips of x per tile
+    constexpr int XREG = (gpos(256 * XS) + 63) / 64 * 64;
+    constexpr int GREG = (gpos(kTileOut) + 63) / 64 * 64;
+    constexpr int NG = KB4 + 4;                      // 4-float groups in a lane's window of x
+    __shared__ __attribute__((aligned(16))) float lds[kWavesPerWg * (XREG + GREG)];
+    __shared__ float red[kWavesPerWg][K4];
+
+    const int64_t unit = blockIdx.x;
+    if (unit >= n_units) return;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    float *X = lds + wave * (XREG + GREG), *G = X + XREG;
+    // consecutive workgroups take consecutive channels of the same images: adjacent rows of memory
+    const int co = (int)(unit % Cout);
+    const int b0 = (int)(unit / Cout) * bgroup;
+    int b1 = b0 + bgroup;
+    if (b1 > B) b1 = B;
+    const int ci = co / cog;
+
+    float acc[K4];
+#pragma unroll
+    for (int t = 0; t < K4; ++t) acc[t] = 0.0f;
+
+    const int n_tiles = (b1 - b0) * tiles_per_row;
+    for (int j = wave; j < n_tiles; j += kWavesPerWg) {
+        const int b = b0 + j / tiles_per_row;
+        const int t0 = (j % tiles_per_row) * kTileOut;
+        const float *xr = x + ((int64_t)b * Cin + ci) * L;
+        const float *gr = gy + ((int64_t)b * Cout + co) * Lo;
+        stage_row<XS>(X, xr, t0 - pad, L, lane);
+        stage_row<kTileOut / 256>(G, gr, t0, Lo, lane);
+        wave_lds_sync();
+        float gv[16], xw[4 * NG];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const v4f g = *(const v4f *)(G + 20 * lane + 4 * u);
+            gv[4 * u] = g.x; gv[4 * u + 1] = g.y; gv[4 * u + 2] = g.z; gv[4 * u + 3] = g.w;
+        }
+#pragma unroll
+        for (int u = 0; u < NG; ++u) {
+            const v4f g = *(const v4f *)(X + 20 * lane + 20 * (u >> 2) + 4 * (u & 3));
+            xw[4 * u] = g.x; xw[4 * u + 1] = g.y; xw[4 * u + 2] = g.z; xw[4 * u + 3] = g.w;
+        }
+#pragma unroll
+        for (int t = 0; t < K4; ++t) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[t] = __builtin_fmaf(gv[e], xw[e + t], acc[t]);
+        }
+        wave_lds_sync();                             // the next tile overwrites X and G
+    }
+    // ---- one total per tap: across lanes, then across the workgroup's wavefronts, then to memory
+#pragma unroll
+    for (int t = 0; t < K4; ++t) {
+        float v = acc[t];
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+        if (lane == 0) red[wave][t] = v;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < k) {
+        float v = 0.0f;
+#pragma unroll
+        for (int wv = 0; wv < kWavesPerWg; ++wv) v += red[wv][threadIdx.x];
+        atomicAdd(gw + (int64_t)co * k + threadIdx.x, v);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Dense channels (groups = 1), stride 1: per tap a 32 x 32 block of gw on the matrix cores.
+// ---------------------------------------------------------------------------------------------
+// A workgroup owns output channels [co0, co0+32), input channels [ci0, ci0+32) and KT taps from
+// t0 on.  The contraction index is (image, position); it is split first over workgroups and then
+// over the four wavefronts of a workgroup: wavefront w takes every fourth slab of 64 positions of
+// the workgroup's range, stages GY[32][64] and X[32][64 + (KT-1)*d] (zero outside the rows) in its
+// own LDS slice (row pitch = 2 mod 64: the 64 lanes of an operand read, 32 rows x 2 adjacent
+// positions, hit 64 banks), the next slab's global loads in flight during the matrix work.  At
+// the end the four accumulator sets are added through LDS and leave as atomic adds whose lanes run
+// over (ci, tap), i.e. over contiguous memory.  Adds to one cache line serialise (measured
+// roughly 0.1 us each), so the number of workgroups per block is kept near what fills the device.
+constexpr int kPw = 64;                              // positions per wavefront slab
+constexpr int kGPitch = kPw + 2;
+
+template <int KT, int XC>
+__global__ __launch_bounds__(kThreads) void conv1d_dense_grad_weight_kernel(
+    const float *__restrict__ x, const float *__restrict__ gy, float *__restrict__ gw, int Cin, int L, int Cout,
+    int Lo, int k, int pad, int dilation, int XPITCH, int slabs_per_row, int64_t total_slabs, int slabs,
+    int co_blocks, int ci_blocks, int tap_groups)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds_dyn[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+    const int slice = 32 * kGPitch + 32 * XPITCH;
+    float *Gl = lds_dyn + wave * slice;              // [32][kGPitch]
+    float *Xl = Gl + 32 * kGPitch;                   // [32][XPITCH]
+
+    int64_t u = blockIdx.x;
+    const int tg = (int)(u % tap_groups); u /= tap_groups;
+    const int cib = (int)(u % ci_blocks); u /= ci_blocks;
+    const int cob = (int)(u % co_blocks); u /= co_blocks;
+    const int64_t slab0 = u * slabs;
+    int64_t slab1 = slab0 + slabs;
+    if (slab1 > total_slabs) slab1 = total_slabs;
+    const int co0 = cob * 32, ci0 = cib * 32, t0 = tg * KT;
+    const int nt = (k - t0 < KT) ? k - t0 : KT;      // live taps of this group
+    const int xw = kPw + (KT - 1) * dilation;        // staged x positions per slab
+    // staging plan: 16 lanes per row of 64 positions (one float4 each), 4 rows per pass;
+    // x rows are xw long: XV passes of 16 float4 columns
+    const int srow = lane >> 4, scol = 4 * (lane & 15);
+    constexpr int GV = 8;                            // 32 rows / 4
+    constexpr int XCMAX = XC;                        // 64-position column blocks of an x row: ceil(xw / 64)
+
+    v16f acc[KT];
+#pragma unroll
+    for (int t = 0; t < KT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+
+    v4f greg[GV], xreg[XCMAX][GV];
+    auto load4 = [&](const float *row, int j, int n, bool row_ok) -> v4f {
+        // elements j .. j+3 of a row of n elements, zero outside
+        if (row_ok && j >= 0 && j + 4 <= n) return *(const v4f_u *)(row + j);
+        v4f r;
+        r.x = (row_ok && j >= 0 && j < n) ? row[j] : 0.0f;
+        r.y = (row_ok && j + 1 >= 0 && j + 1 < n) ? row[j + 1] : 0.0f;
+        r.z = (row_ok && j + 2 >= 0 && j + 2 < n) ? row[j + 2] : 0.0f;
+        r.w = (row_ok && j + 3 >= 0 && j + 3 < n) ? row[j + 3] : 0.0f;
+        return r;
+    };
+    auto prefetch = [&](int64_t slab) {
+        const int64_t b = slab / slabs_per_row;
+        const int i0 = (int)(slab - b * slabs_per_row) * kPw;
+        const int j0 = i0 + t0 * dilation - pad;
+#pragma unroll
+        for (int p = 0; p < GV; ++p) {
+            const int row = 4 * p + srow;
+            const int co = co0 + row, ci = ci0 + row;
+            greg[p] = load4(gy + (b * Cout + (co < Cout ? co : 0)) * (int64_t)Lo, i0 + scol, Lo, co < Cout);
+#pragma unroll
+            for (int c = 0; c < XCMAX; ++c) {
+                xreg[c][p] = load4(x + (b * Cin + (ci < Cin ? ci : 0)) * (int64_t)L, j0 + 64 * c + scol, L, ci < Cin);
+            }
+        }
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int p = 0; p < GV; ++p) {
+            const int row = 4 * p + srow;
+            float *gd = Gl + row * kGPitch + scol;
+            gd[0] = greg[p].x; gd[1] = greg[p].y; gd[2] = greg[p].z; gd[3] = greg[p].w;
+#pragma unroll
+            for (int c = 0; c < XCMAX; ++c) {
+                const int col = 64 * c + scol;
+                float *xd = Xl + row * XPITCH + col;
+                if (col + 0 < xw) xd[0] = xreg[c][p].x;
+                if (col + 1 < xw) xd[1] = xreg[c][p].y;
+                if (col + 2 < xw) xd[2] = xreg[c][p].z;
+                if (col + 3 < xw) xd[3] = xreg[c][p].w;
+            }
+        }
+    };
+
+    int64_t slab = slab0 + wave;
+    if (slab < slab1) prefetch(slab);
+    for (; slab < slab1; slab += kWavesPerWg) {
+        commit();
+        wave_lds_sync();
+        if (slab + kWavesPerWg < slab1) prefetch(slab + kWavesPerWg);     // in flight during the matrix work
+        const float *ga = Gl + l32 * kGPitch + half;
+        const float *xb = Xl + l32 * XPITCH + half;
+#pragma unroll 4
+        for (int ip = 0; ip < kPw; ip += 2) {
+            const float a = ga[ip];
+#pragma unroll
+            for (int t = 0; t < KT; ++t) {
+                const float bv = xb[ip + t * dilation];
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv, acc[t], 0, 0, 0);
+            }
+        }
+        wave_lds_sync();                             // the next slab overwrites the slice
+    }
+    // ---- add the four wavefronts' accumulators through LDS.  Register v of lane (l32, half) is
+    //      row 8*(v/4) + 4*half + v%4 (co), column l32 (ci); it goes to red[wave][row][ci*KT + t].
+    constexpr int RP = 32 * KT + 1;                  // row pitch of a reduction plane
+    __syncthreads();                                 // every slice is free
+    float *red = lds_dyn + wave * (32 * RP);
+#pragma unroll
+    for (int t = 0; t < KT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[(8 * (v >> 2) + 4 * half + (v & 3)) * RP + l32 * KT + t] = acc[t][v];
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < 32 * 32 * KT; idx += kThreads) {
+        const int row = idx / (32 * KT), rest = idx - row * (32 * KT);      // rest = ci*KT + t
+        const int ci = rest / KT, t = rest - ci * KT;
+        float v = 0.0f;
+#pragma unroll
+        for (int wv = 0; wv < kWavesPerWg; ++wv) v += lds_dyn[wv * (32 * RP) + row * RP + rest];
+        if (co0 + row < Cout && ci0 + ci < Cin && t < nt)
+            atomicAdd(gw + ((int64_t)(co0 + row) * Cin + ci0 + ci) * k + t0 + t, v);
+    }
+}
+
+template <int KB4>
+hipError_t launch_thin_gw(const float *x, const float *gy, float *gw, int B, int Cin, int L, int Cout, int Lo, int k,
+                          int pad, int cog, hipStream_t s)
+{
+    const int tiles_per_row = (Lo + kTileOut - 1) / kTileOut;
+    // images per workgroup: at least 16 tiles per wavefront (the reduction at the end costs about
+    // one tile's worth of work), but keep a few thousand workgroups when the problem allows
+    int bgroup = (64 + tiles_per_row - 1) / tiles_per_row;
+    while (bgroup > 1 && (int64_t)Cout * ((B + bgroup - 1) / bgroup) < 2048) bgroup = (bgroup + 1) / 2;
+    const int64_t n_units = (int64_t)Cout * ((B + bgroup - 1) / bgroup);
+    if (n_units > 2147483647LL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((conv1d_thin_grad_weight_kernel<KB4>), dim3((unsigned)n_units), dim3(kThreads), 0, s, x, gy, gw,
+                       B, Cin, L, Cout, Lo, k, pad, cog, tiles_per_row, bgroup, n_units);
+    return hipGetLastError();
+}
+
+template <int KT>
+hipError_t launch_dense_gw(const float *x, const float *gy, float *gw, int64_t B, int Cin, int L, int Cout, int Lo,
+                           int k, int pad, int dilation, hipStream_t s, bool *taken)
+{
+    const int xw = kPw + (KT - 1) * dilation;
+    const int XPITCH = (xw + 61) / 64 * 64 + 2;      // >= xw, = 2 mod 64
+    const size_t stage = (size_t)kWavesPerWg * (32 * kGPitch + 32 * XPITCH) * sizeof(float);
+    const size_t red = (size_t)kWavesPerWg * 32 * (32 * KT + 1) * sizeof(float);
+    const size_t lds = stage > red ? stage : red;
+    *taken = lds <= 128 * 1024 && xw <= 256;        // above 64 KB the kernel's LDS limit is raised below
+    if (!*taken) return hipSuccess;
+    const int slabs_per_row = (Lo + kPw - 1) / kPw;
+    const int64_t total_slabs = B * slabs_per_row;
+    const int co_blocks = (Cout + 31) / 32, ci_blocks = (Cin + 31) / 32, tap_groups = (k + KT - 1) / KT;
+    const int64_t blocks = (int64_t)co_blocks * ci_blocks * tap_groups;
+    // slabs per workgroup: at least one per wavefront, and about 512 workgroups in all (measured on
+    // x[16,64,4096], 64 -> 64 channels, k = 3: 47 us with 1024 workgroups, 41 with 512, 70 with 128)
+    int64_t slabs = (total_slabs * blocks + 511) / 512;
+    if (slabs < kWavesPerWg) slabs = kWavesPerWg;
+    if (g_opt.slide_group > 0) slabs = g_opt.slide_group;           // A/B: slabs per workgroup
+    const int64_t grid = blocks * ((total_slabs + slabs - 1) / slabs);
+    if (grid > 2147483647LL || slabs > 2147483647LL) { *taken = false; return hipSuccess; }
+#define SWS_DGW(XC)                                                                                               \
+    case XC:                                                                                                      \
+        if (lds > 64 * 1024) {                                                                                    \
+            const hipError_t ea = hipFuncSetAttribute((const void *)conv1d_dense_grad_weight_kernel<KT, XC>,      \
+                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);      \
+            if (ea != hipSuccess) return ea;                                                                      \
+        }                                                                                                         \
+        hipLaunchKernelGGL((conv1d_dense_grad_weight_kernel<KT, XC>), dim3((unsigned)grid), dim3(kThreads), lds, s, x, \
+                           gy, gw, Cin, L, Cout, Lo, k, pad, dilation, XPITCH, slabs_per_row, total_slabs, (int)slabs, \
+                           co_blocks, ci_blocks, tap_groups);                                                     \
+        break
+    switch ((xw + 63) / 64) {
+        SWS_DGW(1); SWS_DGW(2); SWS_DGW(3); SWS_DGW(4);
+    default: *taken = false; return hipSuccess;
+    }
+#undef SWS_DGW
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_conv1d_grad_input(const float *gy, const float *wgt, float *gx, int64_t B, int64_t Cin, int64_t L,
+                                    int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad,
+                                    int32_t dilation, int32_t groups, hipStream_t s)
+{
+    const int64_t back_pad = (int64_t)dilation * (k - 1) - pad;
+    if (stride == 1 && back_pad >= 0 && g_opt.conv1d_variant != 1) {
+        // the adjoint as a forward call: Cout channels of length Lo in, Cin channels of length L out
+        bool taken = false;
+        const hipError_t e = launch_conv1d(gy, wgt, gx, B, Cout, Lo, Cin, L, k, 1, (int32_t)back_pad, dilation, groups, s,
+                                           1, &taken);
+        if (taken || e != hipSuccess) return e;
+    }
+    int64_t grid = (B * Cin * L + kThreads - 1) / kThreads;
+    if (grid > 1048576) grid = 1048576;
+    hipLaunchKernelGGL(conv1d_grad_input_naive_kernel, dim3((unsigned)grid), dim3(kThreads), 0, s, gy, wgt, gx, B,
+                       (int)Cin, (int)L, (int)Cout, (int)Lo, k, stride, pad, dilation, groups);
+    return hipGetLastError();
+}
+
+hipError_t launch_conv1d_grad_weight(const float *x, const float *gy, float *gw, int64_t B, int64_t Cin, int64_t L,
+                                     int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad,
+                                     int32_t dilation, int32_t groups, hipStream_t s)
+{
+    const int cig = (int)(Cin / groups), cog = (int)(Cout / groups);
+    const int64_t n_gw = Cout * cig * k;
+    const int variant = g_opt.conv1d_variant;        // 1 forces direct evaluation (A/B and tests)
+    if (n_gw > 2147483647LL) return hipErrorInvalidValue;
+    const bool thin_ok = B > 0 && cig == 1 && stride == 1 && dilation == 1 && k <= 64 && B <= 2147483647LL && variant != 1;
+    const bool dense_ok = B > 0 && groups == 1 && stride == 1 && Cin >= 2 && variant != 1;
+    if (thin_ok || dense_ok) {
+        int64_t fg = (n_gw + kThreads - 1) / kThreads;
+        if (fg > 4096) fg = 4096;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)fg), dim3(kThreads), 0, s, gw, n_gw);
+    }
+    if (thin_ok) {
+#define SWS_TGW(KB)                                                                                              \
+    case KB:                                                                                                     \
+        return launch_thin_gw<KB>(x, gy, gw, (int)B, (int)Cin, (int)L, (int)Cout, (int)Lo, k, pad, cog, s)
+        switch ((k + 3) / 4) {
+            SWS_TGW(1); SWS_TGW(2); SWS_TGW(3); SWS_TGW(4); SWS_TGW(5); SWS_TGW(6); SWS_TGW(7); SWS_TGW(8);
+            SWS_TGW(9); SWS_TGW(10); SWS_TGW(11); SWS_TGW(12); SWS_TGW(13); SWS_TGW(14); SWS_TGW(15); SWS_TGW(16);
+        default: break;
+        }
+#undef SWS_TGW
+    }
+    if (dense_ok) {
+        bool taken = false;
+        hipError_t e;
+        // taps per workgroup: all of them up to 4, else groups of 4 (16 accumulator registers per tap)
+        if (k == 1) e = launch_dense_gw<1>(x, gy, gw, B, (int)Cin, (int)L, (int)Cout, (int)Lo, k, pad, dilation, s, &taken);
+        else if (k == 2) e = launch_dense_gw<2>(x, gy, gw, B, (int)Cin, (int)L, (int)Cout, (int)Lo, k, pad, dilation, s, &taken);
+        else if (k == 3) e = launch_dense_gw<3>(x, gy, gw, B, (int)Cin, (int)L, (int)Cout, (int)Lo, k, pad, dilation, s, &taken);
+        else e = launch_dense_gw<4>(x, gy, gw, B, (int)Cin, (int)L, (int)Cout, (int)Lo, k, pad, dilation, s, &taken);
+        if (taken || e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(conv1d_grad_weight_naive_kernel, dim3((unsigned)n_gw), dim3(kThreads), 0, s, x, gy, gw, B,
+                       (int)Cin, (int)L, (int)Cout, (int)Lo, k, stride, pad, dilation, groups);
+    return hipGetLastError();
+}
+
+}  // namespace sws

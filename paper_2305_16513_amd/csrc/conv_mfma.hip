@@ -40,6 +40,7 @@ struct ConvGeom {
     int sh, sw;                                       // strides (the channel-fastest kernel only)
     int dh, dw;                                       // tap spacing (ditto)
     int wstride, wofs;                                // taps per (co, ci) pair in memory; first tap of this launch
+    int wadj;                                         // weights read as the adjoint's: wgt[ci][co][last tap - t]
     int accum;                                        // add to what y already holds (a later chunk of taps)
     int mode_b;                                       // 0: flat tiles over rows, 1: column tiles of one row
     int NP;                                           // output positions per workgroup
@@ -347,7 +348,14 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
     const int w_co = (threadIdx.x >> 3) & (kCoTile - 1), w_ci = threadIdx.x & 7;
     const bool w_mine = threadIdx.x < kCoTile * 8;    // the first 512 threads move the weights
     const bool w_ok = w_mine && co0 + w_co < g.Cout;
-    const float *wsrc = wgt + (w_ok ? ((int64_t)(co0 + w_co) * g.Cin + w_ci) * g.wstride + g.wofs : 0);
+    // Plain view: wgt[co][ci][wofs + t].  Adjoint view (the convolution that maps output gradients
+    // back to the input): this launch's output channel co is the stored array's input channel, so
+    // the element is wgt[ci][co][wstride - 1 - wofs - t] with rows of g.Cout pairs.
+    const int64_t w_sci = g.wadj ? (int64_t)g.Cout * g.wstride : g.wstride;
+    const int w_st = w_ok ? (g.wadj ? -1 : 1) : 0;   // threads without a pair re-read element 0
+    const float *wsrc = wgt + (w_ok ? (g.wadj ? (int64_t)w_ci * w_sci + (int64_t)(co0 + w_co) * g.wstride + g.wstride - 1 - g.wofs
+                                              : ((int64_t)(co0 + w_co) * g.Cin + w_ci) * g.wstride + g.wofs)
+                                    : 0);
     float *wdst = Wl + w_co * XP + w_ci;
 
     float xreg[NB][XS], wreg[NB][KTMAX];
@@ -361,9 +369,9 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
             const int xb = (ci0 + nb * CIB) * plane;
 #pragma unroll
             for (int s = 0; s < XS; ++s) xreg[nb][s] = xn[xg[s] >= 0 ? xb + xg[s] : 0];
-            const float *w = wsrc + (w_ok ? (ci0 + nb * CIB) * g.wstride : 0);
+            const float *w = wsrc + (w_ok ? (ci0 + nb * CIB) * w_sci : 0);
 #pragma unroll
-            for (int t = 0; t < KTMAX; ++t) wreg[nb][t] = w[t < KT ? t : 0];
+            for (int t = 0; t < KTMAX; ++t) wreg[nb][t] = w[(t < KT ? t : 0) * w_st];
         }
     };
     auto commit = [&]() {
@@ -566,7 +574,8 @@ hipError_t c8_launch(const C8Launch &L, const float *x, const float *wgt, float 
 // these kernels cover and nothing was launched.
 hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
                               int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh,
-                              int32_t sw, int32_t ph, int32_t pw, int32_t dh, int32_t dw, hipStream_t s, bool *taken)
+                              int32_t sw, int32_t ph, int32_t pw, int32_t dh, int32_t dw, hipStream_t s, bool *taken,
+                              int wadj)
 {
     *taken = false;
     const bool plain = sh == 1 && sw == 1 && dh == 1 && dw == 1;
@@ -575,10 +584,10 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
     ConvGeom g;
     g.Cin = (int)Cin; g.H = (int)H; g.W = (int)W; g.Cout = (int)Cout; g.Ho = (int)Ho; g.Wo = (int)Wo;
     g.kh = kh; g.kw = kw; g.ph = ph; g.pw = pw; g.sh = sh; g.sw = sw; g.dh = dh; g.dw = dw;
-    g.wstride = KT; g.wofs = 0; g.accum = 0;
+    g.wstride = KT; g.wofs = 0; g.accum = 0; g.wadj = wadj;
     // Up to 36 adjacent taps at stride 1 the scalar-read kernel does the whole kernel in one pass,
     // which beats a chain of five or more launches (5 x 5 on [32,64,56,56]: 0.27 ms against 0.41 ms).
-    const bool one_pass = plain && KT > 9 && KT <= 36 && Cin % 4 == 0 && g_opt.conv2d_variant != 6;
+    const bool one_pass = !wadj && plain && KT > 9 && KT <= 36 && Cin % 4 == 0 && g_opt.conv2d_variant != 6;
     // preferred: channel-fastest tiles with 128-bit operand reads (Cin % 8 == 0)
     if (!one_pass && Cin % 8 == 0 && g_opt.conv2d_variant != 3 && g_opt.conv2d_variant != 4 &&
         (KT <= 9 || kh == 1 || kw <= 9)) {
@@ -610,7 +619,7 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
             }
         }
     }
-    if (!plain) return hipSuccess;                    // the scalar-read kernels below: stride 1, taps adjacent
+    if (!plain || wadj) return hipSuccess;            // the scalar-read kernels below: stride 1, taps adjacent, plain weights
     // channel blocks of 16 (or 4 for big kernels / odd channel counts) must divide Cin
     const int CIB = (KT <= 9 && Cin % 16 == 0) ? 16 : ((KT <= 36 && Cin % 4 == 0) ? 4 : 0);
     if (CIB == 0) return hipSuccess;

@@ -146,56 +146,12 @@ template <> struct SegStep<SWS_OP_MIN> {
     }
 };
 
-// Element types in memory.  The arithmetic is fp32 whatever the storage type: 16-bit elements are
-// widened on the way into LDS and rounded (to nearest even) once, on the way out.  LINE is the
-// number of elements in a 64-byte line (tile origins are pulled back to such a boundary of y).
-template <typename T> struct Io;
-template <> struct Io<float> {
-    static constexpr int LINE = 16;
-    static __device__ __forceinline__ v4f load4(const float *p) { return *(const v4f_u *)p; }
-    static __device__ __forceinline__ float load1(const float *p) { return *p; }
-    static __device__ __forceinline__ void store1(float *p, float v) { *p = v; }
-    static __device__ __forceinline__ void store4(float *p, v4f o, bool nt)
-    {
-        if (nt) __builtin_nontemporal_store(o, (v4f_u *)p);
-        else *(v4f_u *)p = o;
-    }
-};
-template <> struct Io<__bf16> {
-    static constexpr int LINE = 32;
-    typedef __bf16 v4 __attribute__((ext_vector_type(4)));
-    typedef v4 v4_u __attribute__((aligned(2)));
-    static __device__ __forceinline__ v4f load4(const __bf16 *p) { return __builtin_convertvector(*(const v4_u *)p, v4f); }
-    static __device__ __forceinline__ float load1(const __bf16 *p) { return (float)*p; }
-    static __device__ __forceinline__ void store1(__bf16 *p, float v) { *p = (__bf16)v; }
-    static __device__ __forceinline__ void store4(__bf16 *p, v4f o, bool nt)
-    {
-        const v4 h = __builtin_convertvector(o, v4);
-        if (nt) __builtin_nontemporal_store(h, (v4_u *)p);
-        else *(v4_u *)p = h;
-    }
-};
-template <> struct Io<_Float16> {
-    static constexpr int LINE = 32;
-    typedef _Float16 v4 __attribute__((ext_vector_type(4)));
-    typedef v4 v4_u __attribute__((aligned(2)));
-    static __device__ __forceinline__ v4f load4(const _Float16 *p) { return __builtin_convertvector(*(const v4_u *)p, v4f); }
-    static __device__ __forceinline__ float load1(const _Float16 *p) { return (float)*p; }
-    static __device__ __forceinline__ void store1(_Float16 *p, float v) { *p = (_Float16)v; }
-    static __device__ __forceinline__ void store4(_Float16 *p, v4f o, bool nt)
-    {
-        const v4 h = __builtin_convertvector(o, v4);
-        if (nt) __builtin_nontemporal_store(h, (v4_u *)p);
-        else *(v4_u *)p = h;
-    }
-};
-
 // MODE 0: plain rows.  MODE 1: rows extended by a boundary rule.  MODE 2: one link of a chain of
 // windows (see launch_chain): rows `pitch` apart of which `len` elements are used, results
 // combined with what an earlier link left in y.
-template <int OP, int C, int MODE, typename T>
-__global__ __launch_bounds__(kThreads) void slide_scan_kernel(const T *__restrict__ x,
-                                                              T *__restrict__ y, int len, int lo, int S,
+template <int OP, int C, int MODE>
+__global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__restrict__ x,
+                                                              float *__restrict__ y, int len, int lo, int S,
                                                               float scale, int tiles_per_row, int tout,
                                                               int group, int64_t n_tiles, int64_t n_units,
                                                               int flags, int pad_left_arg, int pad_mode_arg,
@@ -211,7 +167,6 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const T *__restric
     const bool chain_acc = MODE == 2 && (pad_mode_arg & 1);   // combine with the earlier links' result in y
     using O = Op<OP>;
     using G = SegStep<OP>;
-    using IO = Io<T>;
     static_assert(C == 16, "the LDS layout assumes 16-element chunks");
     constexpr int N = kWave * C;                    // inputs per wave tile
     constexpr int NS = C / 4;                       // 256-element strips per tile
@@ -275,22 +230,22 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const T *__restric
     const int pre_pos0 = lds_pos(4 * (lane + s4)), pre_pos1 = lds_pos(4 * (lane + s4 + 1));
 
     for (; gt < gt_end; gt += kWavesPerWg) {
-        const T *xr = x + r * (int64_t)pitch;
-        // With aligned tiles the origin is pulled back so that (r*lo + t0) is a multiple of 64
-        // bytes: every strip store then starts on a 64-byte line.  The first tile of a row
+        const float *xr = x + r * (int64_t)pitch;
+        // With aligned tiles the origin is pulled back so that (r*lo + t0) is a multiple of 16
+        // floats: every 1 KB strip store then starts on a 64-byte line.  The first tile of a row
         // may start before the row (t0 < 0); those outputs are not stored.
-        const int t0 = t * tout - (aligned ? (int)((r * lo) & (IO::LINE - 1)) : 0);
+        const int t0 = t * tout - (aligned ? (int)((r * lo) & 15) : 0);
         const int qlo = t0 < 0 ? -t0 : 0;
         // tile-relative bases: uniform 64-bit arithmetic once, 32-bit lane offsets afterwards
-        const T *xt = xr + (t0 - pad_left);
-        T *yt = y + r * (int64_t)lo + t0;
+        const float *xt = xr + (t0 - pad_left);
+        float *yt = y + r * (int64_t)lo + t0;
         // ---- stage the tile: coalesced strips -> LDS; boundary rule in the padding, identity
         //      outside the extended row
         if (t0 - pad_left >= 0 && t0 - pad_left <= len - N) {
 #pragma unroll
             for (int j = 0; j < NS; ++j) {
                 const int q = j * 256 + 4 * lane;
-                *(v4f *)(A + strip_pos + 256 * j) = IO::load4(xt + q);
+                *(v4f *)(A + strip_pos + 256 * j) = *(const v4f_u *)(xt + q);
             }
         } else {
             // a tile at an end of its row: strip by strip (wave-uniform tests) — whole strips inside
@@ -301,7 +256,7 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const T *__restric
                 const int q = j * 256 + 4 * lane;
                 const int s0 = t0 - pad_left + j * 256;          // physical index of the strip's first element
                 if (s0 >= 0 && s0 + 256 <= len) {
-                    g4[j] = IO::load4(xt + q);
+                    g4[j] = *(const v4f_u *)(xt + q);
                 } else if (!PADDED && (s0 >= len || s0 + 256 <= 0)) {
                     g4[j] = (v4f){O::id(), O::id(), O::id(), O::id()};
                 } else {
@@ -310,7 +265,7 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const T *__restric
                     for (int c = 0; c < 4; ++c) {
                         const int e = t0 + q + c;    // element of the extended row
                         const int src = (e >= 0 && e < lv) ? pad_src(e, len, pad_left, pad_mode) : -1;
-                        e4[c] = src >= 0 ? IO::load1(xr + src) : O::id();
+                        e4[c] = src >= 0 ? xr[src] : O::id();
                     }
                     g4[j] = (v4f){e4[0], e4[1], e4[2], e4[3]};
                 }
@@ -384,24 +339,25 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const T *__restric
             } else {
                 if (chain_acc) {                     // earlier links cover older elements: they go on the left
                     if (q >= qlo && q + 4 <= lim) {
-                        const v4f old = IO::load4(yt + q);
+                        const v4f old = *(const v4f_u *)(yt + q);
                         o.x = O::f(old.x, o.x); o.y = O::f(old.y, o.y); o.z = O::f(old.z, o.z); o.w = O::f(old.w, o.w);
                     } else {
-                        if (q + 0 >= qlo && q + 0 < lim) o.x = O::f(IO::load1(yt + q + 0), o.x);
-                        if (q + 1 >= qlo && q + 1 < lim) o.y = O::f(IO::load1(yt + q + 1), o.y);
-                        if (q + 2 >= qlo && q + 2 < lim) o.z = O::f(IO::load1(yt + q + 2), o.z);
-                        if (q + 3 >= qlo && q + 3 < lim) o.w = O::f(IO::load1(yt + q + 3), o.w);
+                        if (q + 0 >= qlo && q + 0 < lim) o.x = O::f(yt[q + 0], o.x);
+                        if (q + 1 >= qlo && q + 1 < lim) o.y = O::f(yt[q + 1], o.y);
+                        if (q + 2 >= qlo && q + 2 < lim) o.z = O::f(yt[q + 2], o.z);
+                        if (q + 3 >= qlo && q + 3 < lim) o.w = O::f(yt[q + 3], o.w);
                     }
                 }
                 if (OP == SWS_OP_ADD) o *= scale;    // 1 in every link but the last
             }
             if (q >= qlo && q + 4 <= lim) {
-                IO::store4(yt + q, o, (flags & 2) != 0);
+                if (flags & 2) __builtin_nontemporal_store(o, (v4f_u *)(yt + q));
+                else *(v4f_u *)(yt + q) = o;
             } else {
-                if (q + 0 >= qlo && q + 0 < lim) IO::store1(yt + q + 0, o.x);
-                if (q + 1 >= qlo && q + 1 < lim) IO::store1(yt + q + 1, o.y);
-                if (q + 2 >= qlo && q + 2 < lim) IO::store1(yt + q + 2, o.z);
-                if (q + 3 >= qlo && q + 3 < lim) IO::store1(yt + q + 3, o.w);
+                if (q + 0 >= qlo && q + 0 < lim) yt[q + 0] = o.x;
+                if (q + 1 >= qlo && q + 1 < lim) yt[q + 1] = o.y;
+                if (q + 2 >= qlo && q + 2 < lim) yt[q + 2] = o.z;
+                if (q + 3 >= qlo && q + 3 < lim) yt[q + 3] = o.w;
             }
         }
         wave_lds_sync();                                         // the next tile overwrites A
@@ -437,24 +393,24 @@ hipError_t launch_direct(const float *x, float *y, int64_t rows, int len, int lo
 // slide_chunk option bits (A/B measurements): 1 = never align tiles, 2 = plain instead of
 // non-temporal stores on aligned tiles, 4 = force the XCD-contiguous unit mapping on,
 // 8 = force it off.
-template <int OP, typename T>
-hipError_t launch_scan(const T *x, T *y, int64_t rows, int len, int lo, int w, float scale,
+template <int OP>
+hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, int w, float scale,
                        int pad_left, int pad_mode, int lv, hipStream_t s, int chain = 0, int pitch = 0)
 {
-    constexpr int C = 16, N = kWave * C, LINE = Io<T>::LINE;
+    constexpr int C = 16, N = kWave * C;
     const int S = w - 1;
     const int max_tout = N - S;
     const int opt = g_opt.slide_chunk;
     int flags = 0;
     // Unaligned plan: as few tiles per row as possible.  Aligned plan (preferred; measured
-    // faster even when it costs one more tile per row): tile length a multiple of 64 bytes and
+    // faster even when it costs one more tile per row): tile length a multiple of 16 floats and
     // origins pulled back per row so that every strip store starts on a 64-byte line of y,
     // which also makes non-temporal stores pay off.
     int tiles = (lo + max_tout - 1) / max_tout;
     int tout = (lo + tiles - 1) / tiles;
-    if (!(opt & 1) && max_tout >= LINE) {
-        tout = max_tout & ~(LINE - 1);
-        tiles = (lo + LINE - 1 + tout - 1) / tout;
+    if (!(opt & 1) && max_tout >= 16) {
+        tout = max_tout & ~15;
+        tiles = (lo + 15 + tout - 1) / tout;
         flags |= 4;
         if (!(opt & 2)) flags |= 2;
     }
@@ -472,19 +428,15 @@ hipError_t launch_scan(const T *x, T *y, int64_t rows, int len, int lo, int w, f
     const int64_t n_units = (n_tiles + g - 1) / g;
     const int64_t grid = remap ? xcd_grid(n_units) : n_units;
     if (grid > 2147483647LL) return hipErrorInvalidValue;
-    if constexpr (sizeof(T) != 4) {                   // 16-bit elements: plain rows only
-        if (chain || lv != len) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((slide_scan_kernel<OP, C, 0, T>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
-                           S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, 0, 0, len);
-    } else if (chain) {                               // chain bits: 1 = combine with y, 2 = last link
+    if (chain) {                                      // chain bits: 1 = combine with y, 2 = last link
         if (!(chain & 2)) flags &= ~2;                // y is read again by the next link: plain stores
-        hipLaunchKernelGGL((slide_scan_kernel<OP, C, 2, T>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
+        hipLaunchKernelGGL((slide_scan_kernel<OP, C, 2>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
                            S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, 0, chain & 1, pitch);
     } else if (lv != len) {
-        hipLaunchKernelGGL((slide_scan_kernel<OP, C, 1, T>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
+        hipLaunchKernelGGL((slide_scan_kernel<OP, C, 1>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
                            S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, pad_left, pad_mode, lv);
     } else {
-        hipLaunchKernelGGL((slide_scan_kernel<OP, C, 0, T>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
+        hipLaunchKernelGGL((slide_scan_kernel<OP, C, 0>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
                            S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, 0, 0, len);
     }
     return hipGetLastError();
@@ -508,7 +460,7 @@ hipError_t launch_chain(const float *x, float *y, int64_t rows, int len, int lo,
     for (int j = 0; j < links; ++j) {
         const int wj = (w - done) / (links - j);    // near-equal widths, each >= 2
         const bool last = j == links - 1;
-        const hipError_t e = launch_scan<OP, float>(x + done, y, rows, lo + wj - 1, lo, wj, last ? scale : 1.0f, 0, 0,
+        const hipError_t e = launch_scan<OP>(x + done, y, rows, lo + wj - 1, lo, wj, last ? scale : 1.0f, 0, 0,
                                              lo + wj - 1, s, 4 | (j > 0 ? 1 : 0) | (last ? 2 : 0), len);
         if (e != hipSuccess) return e;
         done += wj;
@@ -516,61 +468,11 @@ hipError_t launch_chain(const float *x, float *y, int64_t rows, int len, int lo,
     return hipSuccess;
 }
 
-// Direct evaluation on 16-bit elements (w = 1 and windows beyond the scan kernel's reach): one
-// thread per output, fp32 accumulation left to right, one rounding at the end.
-template <int OP, typename T>
-__global__ __launch_bounds__(kThreads) void slide16_naive_kernel(const T *__restrict__ x, T *__restrict__ y,
-                                                                 int64_t rows, int len, int lo, int w, float scale)
-{
-    using O = Op<OP>;
-    const int64_t total = rows * (int64_t)lo;
-    for (int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x; o < total; o += (int64_t)gridDim.x * kThreads) {
-        const int64_t r = o / lo;
-        const T *xr = x + r * (int64_t)len + (o - r * lo);
-        float acc = (float)xr[0];
-        for (int j = 1; j < w; ++j) acc = O::f(acc, (float)xr[j]);
-        if (OP == SWS_OP_ADD) acc *= scale;
-        y[o] = (T)acc;
-    }
-}
-
 constexpr int kDirectMaxW = 9;
 constexpr int kScanMaxW = kWave * 16 - 64 + 1;      // leaves at least 64 outputs per wave tile
 constexpr int kChainMinW = 850;                     // longer windows run as a chain of shorter ones
 
-template <int OP, typename T>
-hipError_t launch_16(const T *x, T *y, int64_t rows, int len, int lo, int w, float scale, hipStream_t s)
-{
-    if (w >= 2 && w <= kScanMaxW && g_opt.slide_variant != 1)
-        return launch_scan<OP, T>(x, y, rows, len, lo, w, scale, 0, 0, len, s);
-    int64_t grid = (rows * (int64_t)lo + kThreads - 1) / kThreads;
-    if (grid > 1048576) grid = 1048576;
-    hipLaunchKernelGGL((slide16_naive_kernel<OP, T>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, rows, len, lo,
-                       w, scale);
-    return hipGetLastError();
-}
-
-template <typename T>
-hipError_t launch_16_op(int op, const void *x, void *y, int64_t rows, int len, int lo, int w, float scale,
-                        hipStream_t s)
-{
-    switch (op) {
-    case SWS_OP_ADD: return launch_16<SWS_OP_ADD, T>((const T *)x, (T *)y, rows, len, lo, w, scale, s);
-    case SWS_OP_MAX: return launch_16<SWS_OP_MAX, T>((const T *)x, (T *)y, rows, len, lo, w, scale, s);
-    default: return launch_16<SWS_OP_MIN, T>((const T *)x, (T *)y, rows, len, lo, w, scale, s);
-    }
-}
-
 }  // namespace
-
-// 16-bit storage (dtype SWS_DTYPE_BF16 / SWS_DTYPE_F16), fp32 arithmetic, one rounding per output.
-hipError_t launch_slide1d_16(int op, int dtype, const void *x, void *y, int64_t rows, int64_t len64, int32_t w,
-                             float scale, hipStream_t s)
-{
-    const int len = (int)len64, lo = len - w + 1;
-    if (dtype == SWS_DTYPE_BF16) return launch_16_op<__bf16>(op, x, y, rows, len, lo, w, scale, s);
-    return launch_16_op<_Float16>(op, x, y, rows, len, lo, w, scale, s);
-}
 
 hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_t len64, int32_t w,
                           int32_t pad_left, int32_t pad_right, int pad_mode, float scale, hipStream_t s)
@@ -612,9 +514,9 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
         }
     }
     switch (op) {
-    case SWS_OP_ADD: return launch_scan<SWS_OP_ADD, float>(x, y, rows, len, lo, w, scale, pad_left, pad_mode, lv, s);
-    case SWS_OP_MAX: return launch_scan<SWS_OP_MAX, float>(x, y, rows, len, lo, w, scale, pad_left, pad_mode, lv, s);
-    default: return launch_scan<SWS_OP_MIN, float>(x, y, rows, len, lo, w, scale, pad_left, pad_mode, lv, s);
+    case SWS_OP_ADD: return launch_scan<SWS_OP_ADD>(x, y, rows, len, lo, w, scale, pad_left, pad_mode, lv, s);
+    case SWS_OP_MAX: return launch_scan<SWS_OP_MAX>(x, y, rows, len, lo, w, scale, pad_left, pad_mode, lv, s);
+    default: return launch_scan<SWS_OP_MIN>(x, y, rows, len, lo, w, scale, pad_left, pad_mode, lv, s);
     }
 }
 

@@ -166,6 +166,51 @@ sws_status sws_conv1d(const float *x, const float *wgt, float *y, int64_t B, int
                                        (hipStream_t)stream));
 }
 
+namespace {
+
+// Shared argument checks of the convolution and its adjoints; *Lo receives the output length.
+sws_status check_conv1d(int64_t B, int64_t Cin, int64_t L, int64_t Cout, int32_t k, int32_t stride, int32_t pad,
+                        int32_t dilation, int32_t groups, int64_t *Lo)
+{
+    if (B < 0 || Cin < 1 || L < 0 || Cout < 1 || k < 1 || stride < 1 || pad < 0 || dilation < 1 || groups < 1)
+        return SWS_ERR_INVALID_ARG;
+    if (Cin % groups || Cout % groups || L > kMaxDim || Cin > kMaxDim || Cout > kMaxDim)
+        return SWS_ERR_INVALID_ARG;
+    *Lo = sws_out_len(L, k, stride, pad, dilation);
+    if (*Lo < 1) return SWS_ERR_INVALID_ARG;
+    int64_t n_in, n_out, n_w;
+    if (!mul3(B, Cin, L, &n_in) || !mul3(B, Cout, *Lo, &n_out) || !mul3(Cout, Cin / groups, k, &n_w))
+        return SWS_ERR_INVALID_ARG;
+    return SWS_OK;
+}
+
+}  // namespace
+
+sws_status sws_conv1d_grad_input(const float *gy, const float *wgt, float *gx, int64_t B, int64_t Cin, int64_t L,
+                                 int64_t Cout, int32_t k, int32_t stride, int32_t pad, int32_t dilation,
+                                 int32_t groups, void *stream)
+{
+    int64_t Lo;
+    const sws_status st = check_conv1d(B, Cin, L, Cout, k, stride, pad, dilation, groups, &Lo);
+    if (st != SWS_OK) return st;
+    if (B == 0) return SWS_OK;
+    if (!gy || !wgt || !gx) return SWS_ERR_INVALID_ARG;
+    return from_hip(sws::launch_conv1d_grad_input(gy, wgt, gx, B, Cin, L, Cout, Lo, k, stride, pad, dilation, groups,
+                                                  (hipStream_t)stream));
+}
+
+sws_status sws_conv1d_grad_weight(const float *x, const float *gy, float *gw, int64_t B, int64_t Cin, int64_t L,
+                                  int64_t Cout, int32_t k, int32_t stride, int32_t pad, int32_t dilation,
+                                  int32_t groups, void *stream)
+{
+    int64_t Lo;
+    const sws_status st = check_conv1d(B, Cin, L, Cout, k, stride, pad, dilation, groups, &Lo);
+    if (st != SWS_OK) return st;
+    if (!gw || (B > 0 && (!x || !gy))) return SWS_ERR_INVALID_ARG;      // with no images gw is all zeros
+    return from_hip(sws::launch_conv1d_grad_weight(x, gy, gw, B, Cin, L, Cout, Lo, k, stride, pad, dilation, groups,
+                                                   (hipStream_t)stream));
+}
+
 sws_status sws_conv2d(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
                       int64_t W, int64_t Cout, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph,
                       int32_t pw, void *stream)

@@ -83,7 +83,14 @@ hipError_t launch_pool2d(int op, const float *x, float *y, int64_t planes, int64
                          int32_t ph, int32_t pw, float scale, hipStream_t s);
 hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin, int64_t L,
                          int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad,
-                         int32_t dilation, int32_t groups, hipStream_t s);
+                         int32_t dilation, int32_t groups, hipStream_t s, int wadj = 0, bool *taken = nullptr);
+// Adjoints of the 1-D convolution (conv_grad.hip).
+hipError_t launch_conv1d_grad_input(const float *gy, const float *wgt, float *gx, int64_t B, int64_t Cin, int64_t L,
+                                    int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad,
+                                    int32_t dilation, int32_t groups, hipStream_t s);
+hipError_t launch_conv1d_grad_weight(const float *x, const float *gy, float *gw, int64_t B, int64_t Cin, int64_t L,
+                                     int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad,
+                                     int32_t dilation, int32_t groups, hipStream_t s);
 hipError_t launch_conv2d(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
                          int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw,
                          int32_t sh, int32_t sw, int32_t ph, int32_t pw, hipStream_t s);
@@ -92,7 +99,7 @@ hipError_t launch_conv2d(const float *x, const float *wgt, float *y, int64_t N, 
 hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
                               int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh,
                               int32_t sw, int32_t ph, int32_t pw, int32_t dh, int32_t dw, hipStream_t s,
-                              bool *taken);
+                              bool *taken, int wadj = 0);
 
 // Direct-evaluation fallbacks (naive_kernels.hip).
 hipError_t launch_slide1d_naive(int op, const float *x, float *y, int64_t rows, int64_t len, int32_t w,

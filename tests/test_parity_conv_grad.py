@@ -1,0 +1,143 @@
+"""GPU parity of the adjoints of sws_conv1d (sws_conv1d_grad_input, sws_conv1d_grad_weight) against the
+CPU oracle's scatter-form definitions, through the C ABI: |err| <= 1e-5 * sum|terms| per element, and
+bit-exact on small-integer data (every fp32 partial sum is exact, whatever the order of the atomic adds)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2305_16513_amd import workloads
+from parity_util import assert_within_tol, to_gpu, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2305_16513_amd import binding
+    binding.lib()
+    yield binding
+    binding.sws_set_option("conv1d_variant", 0)
+
+
+def _lo(length, k, stride, pad, dil):
+    return (length + 2 * pad - dil * (k - 1) - 1) // stride + 1
+
+
+def _data(case, seed, integer=False):
+    b, cin, length, cout, k, stride, pad, dil, groups = case
+    lo = _lo(length, k, stride, pad, dil)
+    if integer:
+        x = workloads.integer_valued((b, cin, length), -3, 3, seed)
+        w = workloads.integer_valued((cout, cin // groups, k), -3, 3, seed + 1)
+        g = workloads.integer_valued((b, cout, lo), -3, 3, seed + 2)
+    else:
+        r = np.random.Generator(np.random.PCG64(seed))
+        x = r.standard_normal((b, cin, length), dtype=np.float32)
+        w = (r.standard_normal((cout, cin // groups, k), dtype=np.float32) * np.float32(0.3)).astype(np.float32)
+        g = r.standard_normal((b, cout, lo), dtype=np.float32)
+    return x, w, g
+
+
+def _check_gx(B, case, seed=0, integer=False):
+    b, cin, length, cout, k, stride, pad, dil, groups = case
+    x, w, g = _data(case, seed, integer)
+    gx = to_host(B.sws_conv1d_grad_input(to_gpu(g), to_gpu(w), length, stride, pad, dil, groups))
+    ref, mag = oracle.conv1d_grad_input(g, w, length, stride, pad, dil, groups)
+    if integer:
+        assert np.array_equal(gx.astype(np.float64), ref), str(case)
+    else:
+        assert_within_tol(gx, ref, mag, "grad_input %s" % (case,))
+
+
+def _check_gw(B, case, seed=0, integer=False):
+    b, cin, length, cout, k, stride, pad, dil, groups = case
+    x, w, g = _data(case, seed, integer)
+    gw = to_host(B.sws_conv1d_grad_weight(to_gpu(x), to_gpu(g), k, stride, pad, dil, groups))
+    ref, mag = oracle.conv1d_grad_weight(x, g, k, stride, pad, dil, groups)
+    if integer:
+        assert np.array_equal(gw.astype(np.float64), ref), str(case)
+    else:
+        assert_within_tol(gw, ref, mag, "grad_weight %s" % (case,))
+
+
+# B, Cin, L, Cout, k, stride, pad, dilation, groups
+THIN = [(3, 8, 5003, 8, 31, 1, 15, 1, 8), (2, 4, 3000, 4, 5, 1, 0, 1, 4), (2, 3, 2500, 3, 64, 1, 7, 1, 3),
+        (2, 2, 1500, 2, 1, 1, 0, 1, 2), (5, 3, 1024, 3, 3, 1, 1, 1, 3), (2, 2, 4100, 6, 7, 1, 3, 1, 2),
+        (1, 1, 100000, 1, 51, 1, 25, 1, 1)]
+THIN_DILATED = [(2, 4, 3000, 4, 5, 1, 6, 3, 4), (1, 2, 9000, 2, 51, 1, 0, 8, 2), (2, 3, 2000, 3, 100, 1, 50, 1, 3)]
+GROUPED = [(2, 4, 3001, 6, 5, 1, 2, 1, 2), (2, 6, 2000, 3, 9, 1, 4, 1, 3), (2, 15, 1500, 15, 11, 1, 0, 2, 1),
+           (2, 12, 1200, 20, 3, 1, 1, 1, 1)]
+DENSE = [(3, 64, 1000, 64, 3, 1, 1, 1, 1), (2, 16, 700, 24, 5, 1, 2, 1, 1), (2, 72, 333, 136, 3, 1, 0, 1, 1),
+         (2, 32, 900, 32, 4, 1, 3, 2, 1), (1, 8, 2000, 16, 11, 1, 5, 1, 1), (2, 64, 260, 64, 1, 1, 0, 1, 1),
+         (2, 24, 500, 8, 2, 1, 0, 7, 1)]
+DIRECT = [(2, 4, 500, 4, 5, 2, 2, 1, 4), (2, 8, 301, 16, 3, 2, 1, 1, 1), (2, 6, 400, 4, 4, 3, 0, 2, 2),
+          (1, 2, 50, 2, 3, 1, 5, 1, 2)]
+
+
+@pytest.mark.parametrize("case", THIN + THIN_DILATED + GROUPED + DENSE + DIRECT)
+def test_grad_input(B, case):
+    _check_gx(B, case, seed=hash(case) % 1000)
+
+
+@pytest.mark.parametrize("case", THIN + THIN_DILATED + GROUPED + DENSE + DIRECT)
+def test_grad_weight(B, case):
+    _check_gw(B, case, seed=hash(case) % 1000 + 7)
+
+
+@pytest.mark.parametrize("case", [THIN[0], THIN[5], GROUPED[0], DENSE[0], DENSE[1], DENSE[3], DIRECT[1]])
+def test_exact_on_small_integers(B, case):
+    _check_gx(B, case, seed=11, integer=True)
+    _check_gw(B, case, seed=12, integer=True)
+
+
+@pytest.mark.parametrize("case", [THIN[0], DENSE[0], GROUPED[1]])
+def test_tuned_kernels_agree_with_direct_evaluation_on_the_gpu(B, case):
+    """conv1d_variant = 1 forces the direct-evaluation kernels: both must pass against the oracle."""
+    B.sws_set_option("conv1d_variant", 1)
+    try:
+        _check_gx(B, case, seed=21)
+        _check_gw(B, case, seed=22)
+    finally:
+        B.sws_set_option("conv1d_variant", 0)
+
+
+def test_layer_shaped_depthwise(B):
+    """A slice of configuration 5: 128 channels, 16384-long rows, k = 31 (4 images)."""
+    case = (4, 128, 16384, 128, 31, 1, 0, 1, 128)
+    _check_gx(B, case, seed=31)
+    _check_gw(B, case, seed=32)
+
+
+def test_layer_shaped_dense(B):
+    """Configuration 2: x[16,64,4096], 64 -> 64 channels, k = 3."""
+    case = (16, 64, 4096, 64, 3, 1, 0, 1, 1)
+    _check_gx(B, case, seed=33)
+    _check_gw(B, case, seed=34)
+
+
+def test_inner_product_identities_on_the_gpu(B):
+    """<conv(x; W), g> = <x, gx> = <W, gw> with all three computed on the GPU."""
+    case = (2, 32, 1500, 48, 5, 1, 2, 1, 1)
+    x, w, g = _data(case, 40)
+    y = to_host(B.sws_conv1d(to_gpu(x), to_gpu(w), 1, 2, 1, 1)).astype(np.float64)
+    gx = to_host(B.sws_conv1d_grad_input(to_gpu(g), to_gpu(w), 1500, 1, 2, 1, 1)).astype(np.float64)
+    gw = to_host(B.sws_conv1d_grad_weight(to_gpu(x), to_gpu(g), 5, 1, 2, 1, 1)).astype(np.float64)
+    loss = float((y * g).sum())
+    scale = float(np.abs(y * g).sum())
+    assert abs(loss - float((x * gx).sum())) < 1e-5 * scale
+    assert abs(loss - float((w * gw).sum())) < 1e-5 * scale
+
+
+def test_argument_checks(B):
+    import torch
+    g = torch.zeros((2, 4, 98), device="cuda")
+    w = torch.zeros((4, 1, 3), device="cuda")
+    with pytest.raises(B.SwsError):
+        B.sws_conv1d_grad_input(g, w, 101, 1, 0, 1, 4)          # gy is not the forward output's shape
+    L = B.lib()
+    assert L.sws_conv1d_grad_input(g.data_ptr(), w.data_ptr(), None, 2, 4, 100, 4, 3, 1, 0, 1, 4, None) == B.SWS_ERR_INVALID_ARG
+    assert L.sws_conv1d_grad_weight(g.data_ptr(), g.data_ptr(), w.data_ptr(), 2, 4, 100, 4, 3, 0, 0, 1, 4, None) == B.SWS_ERR_INVALID_ARG
+    gw = torch.ones((4, 1, 3), device="cuda")
+    assert L.sws_conv1d_grad_weight(None, None, gw.data_ptr(), 0, 4, 100, 4, 3, 1, 0, 1, 4, None) == B.SWS_OK
+    torch.cuda.synchronize()
+    assert float(gw.abs().sum()) == 0.0
