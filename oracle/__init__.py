@@ -18,12 +18,14 @@ from .ref import (  # noqa: F401
     conv1d_grad_weight,
     conv2d,
     pool2d,
+    pool2d_ex,
     round16,
     set_threads,
     PAD_EDGE,
     PAD_IDENTITY,
     PAD_MIRROR,
     PAD_PERIODIC,
+    PAD_SHRINK,
     slide1d,
     slide1d_padded,
     slide1d_pair,

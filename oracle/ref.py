@@ -45,6 +45,9 @@ def _load():
         lib.sws_ref_pool2d.restype = ctypes.c_int
         lib.sws_ref_pool2d.argtypes = [ctypes.c_int, _fp, _dp, _dp, _i64, _i64, _i64, _i64,
                                        _i32, _i32, _i32, _i32, _i32, _i32, _f64]
+        lib.sws_ref_pool2d_ex.restype = ctypes.c_int
+        lib.sws_ref_pool2d_ex.argtypes = [ctypes.c_int, _fp, _dp, _dp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32,
+                                          _i32, _i32, _i32, _i32, ctypes.c_int, _f64]
         lib.sws_ref_slide1d_padded.restype = ctypes.c_int
         lib.sws_ref_slide1d_padded.argtypes = [ctypes.c_int, _fp, _dp, _dp, _i64, _i64, _i32, _i32, _i32,
                                                ctypes.c_int, _f64]
@@ -119,7 +122,7 @@ def round16(y, dtype):
     return out
 
 
-PAD_IDENTITY, PAD_MIRROR, PAD_PERIODIC, PAD_EDGE = 0, 1, 2, 3
+PAD_IDENTITY, PAD_MIRROR, PAD_PERIODIC, PAD_EDGE, PAD_SHRINK = 0, 1, 2, 3, 4
 
 
 def slide1d_padded(op, x, w, pad_left, pad_right, mode, scale=1.0):
@@ -247,3 +250,22 @@ def conv1d_grad_weight(x, gy, k, stride=1, pad=0, dilation=1, groups=1):
     if rc:
         raise ValueError("sws_ref_conv1d_grad_weight rejected its arguments")
     return gw, s
+
+
+def pool2d_ex(op, x, kh, kw, sh=1, sw=1, pads=(0, 0, 0, 0), div_valid=False, scale=1.0):
+    """x: [N, C, H, W] float32, pads = (top, left, bottom, right) -> (y, abs_sum) [N, C, Ho, Wo] float64.
+    div_valid: ADD results are divided by the number of window cells inside the plane."""
+    x = _f32(x)
+    n, c, h, wd = x.shape
+    pt, pl, pb, pr = pads
+    ho = (h + pt + pb - kh) // sh + 1
+    wo = (wd + pl + pr - kw) // sw + 1
+    if ho < 1 or wo < 1:
+        raise ValueError("window larger than the padded plane")
+    y = np.empty((n, c, ho, wo), np.float64)
+    s = np.empty((n, c, ho, wo), np.float64)
+    rc = _load().sws_ref_pool2d_ex(op, _ptr_f(x), _ptr_d(y), _ptr_d(s), n, c, h, wd, kh, kw, sh, sw, pt, pl, pb, pr,
+                                   1 if div_valid else 0, float(scale))
+    if rc:
+        raise ValueError("sws_ref_pool2d_ex rejected its arguments")
+    return y, s

@@ -19,6 +19,9 @@
  *                    checked against an independent formulation.  Taps that
  *                    fall into the padding contribute the identity of the
  *                    operator (they are skipped).
+ *   sws_ref_pool2d_ex  the same window scan with separate padding on the four sides and, for
+ *                    ADD, the choice of dividing by the number of window cells that lie inside
+ *                    the plane (average pooling that does not count the padding).
  *   sws_ref_slide1d_padded  Eq. 3 on rows extended at both ends (the boundary conditions
  *                    named in Section 3: padding, mirroring, periodicity; plus edge
  *                    replication).  Every window element's index is mapped back into
@@ -285,12 +288,16 @@ int sws_ref_slide1d_pair(const float *u, const float *v, double *yu, double *yv,
 /* Eq. 3 over rows extended by pad_left / pad_right virtual elements.  mode: 0 = the identity of
  * the operator (0 for ADD, -inf for MAX, +inf for MIN; such elements are skipped), 1 = mirror
  * about the end elements without repeating them (x[-i] = x[i]), 2 = periodic (x[-i] = x[len-i]),
- * 3 = the end element repeated.  y, abs_sum: rows*(len+pad_left+pad_right-w+1) doubles. */
+ * 3 = the end element repeated, 4 = the window shrinks at the ends: the virtual elements are
+ * skipped as in mode 0 and an ADD result is multiplied by w / n, n = the number of real elements
+ * in the window (so that scale = 1/w gives the mean over real elements; pads must be < w).
+ * y, abs_sum: rows*(len+pad_left+pad_right-w+1) doubles. */
 int sws_ref_slide1d_padded(int op, const float *x, double *y, double *abs_sum, int64_t rows, int64_t len,
                            int32_t w, int32_t pad_left, int32_t pad_right, int mode, double scale)
 {
-    if (op < 0 || op > 2 || mode < 0 || mode > 3 || rows < 0 || len < 1 || w < 1 || pad_left < 0 || pad_right < 0)
+    if (op < 0 || op > 2 || mode < 0 || mode > 4 || rows < 0 || len < 1 || w < 1 || pad_left < 0 || pad_right < 0)
         return 1;
+    if (mode == 4 && (pad_left >= w || pad_right >= w)) return 1;     /* every window holds a real element */
     const int64_t lv = len + pad_left + pad_right, lo = lv - w + 1;
     if (lo < 1) return 1;
     if (mode == 1 && (pad_left > len - 1 || pad_right > len - 1)) return 1;
@@ -301,23 +308,24 @@ int sws_ref_slide1d_padded(int op, const float *x, double *y, double *abs_sum, i
         const float *xr = x + r * len;
         for (int64_t i = 0; i < lo; ++i) {
             double acc = 0.0, mag = 0.0;
-            int have = 0;
+            int64_t have = 0;                            /* real or mapped elements combined so far */
             for (int32_t t = 0; t < w; ++t) {
                 int64_t p = i + t - pad_left;            /* index into the physical row, may be outside */
                 if (p < 0 || p >= len) {
-                    if (mode == 0) continue;             /* identity element: contributes nothing */
+                    if (mode == 0 || mode == 4) continue;   /* identity element: contributes nothing */
                     if (mode == 1) p = p < 0 ? -p : 2 * (len - 1) - p;
                     else if (mode == 2) p = p < 0 ? p + len : p - len;
                     else p = p < 0 ? 0 : len - 1;
                 }
                 const double v = (double)xr[p];
                 acc = have ? combine(op, acc, v) : v;
-                have = 1;
+                ++have;
                 mag += fabs(v);
             }
             if (!have) acc = op == REF_ADD ? 0.0 : (op == REF_MAX ? -INFINITY : INFINITY);
-            y[r * lo + i] = op == REF_ADD ? acc * scale : acc;
-            if (abs_sum) abs_sum[r * lo + i] = op == REF_ADD ? mag * fabs(scale) : mag;
+            const double f = (mode == 4 && have) ? scale * (double)w / (double)have : scale;
+            y[r * lo + i] = op == REF_ADD ? acc * f : acc;
+            if (abs_sum) abs_sum[r * lo + i] = op == REF_ADD ? mag * fabs(f) : mag;
         }
     }
     return 0;
@@ -421,6 +429,50 @@ int sws_ref_conv1d_grad_weight(const float *x, const float *gy, double *gw, doub
                         gw[(co * cig + ci) * k + t] += term;
                         if (abs_sum) abs_sum[(co * cig + ci) * k + t] += fabs(term);
                     }
+            }
+    }
+    return 0;
+}
+
+/* NCHW pooling with padding pt / pl / pb / pr on the top / left / bottom / right side:
+ * Ho = (H + pt + pb - kh)/sh + 1, Wo = (W + pl + pr - kw)/sw + 1.  Padding holds the identity.
+ * ADD: y = scale * sum when div_valid = 0; y = scale * sum / n when div_valid = 1, n = number of
+ * cells of the window inside the plane (scale = 1: the mean over real cells). */
+int sws_ref_pool2d_ex(int op, const float *x, double *y, double *abs_sum,
+                      int64_t N, int64_t C, int64_t H, int64_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                      int32_t pt, int32_t pl, int32_t pb, int32_t pr, int div_valid, double scale)
+{
+    if (op < 0 || op > 2 || N < 0 || C < 0 || H < 1 || W < 1) return 1;
+    if (kh < 1 || kw < 1 || sh < 1 || sw < 1 || pt < 0 || pl < 0 || pb < 0 || pr < 0) return 1;
+    if (pt >= kh || pb >= kh || pl >= kw || pr >= kw) return 1;      /* every window holds a real cell */
+    if (kh > H + pt + (int64_t)pb || kw > W + pl + (int64_t)pr) return 1;
+    const int64_t Ho = (H + pt + (int64_t)pb - kh) / sh + 1;
+    const int64_t Wo = (W + pl + (int64_t)pr - kw) / sw + 1;
+    const int64_t planes = N * C;
+    if (planes > 0 && (!x || !y)) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t p = 0; p < planes; ++p) {
+        const float *xp = x + p * H * W;
+        for (int64_t ho = 0; ho < Ho; ++ho)
+            for (int64_t wo = 0; wo < Wo; ++wo) {
+                int64_t n = 0;
+                double acc = 0.0, mag = 0.0;
+                for (int32_t a = 0; a < kh; ++a)
+                    for (int32_t b = 0; b < kw; ++b) {
+                        const int64_t h = ho * sh - pt + a, c = wo * sw - pl + b;
+                        if (h < 0 || h >= H || c < 0 || c >= W) continue;
+                        const double v = (double)xp[h * W + c];
+                        acc = n ? combine(op, acc, v) : v;
+                        mag += fabs(v);
+                        ++n;
+                    }
+                if (op == REF_ADD) {
+                    const double f = div_valid ? scale / (double)n : scale;
+                    acc *= f;
+                    mag *= fabs(f);
+                }
+                y[(p * Ho + ho) * Wo + wo] = acc;
+                if (abs_sum) abs_sum[(p * Ho + ho) * Wo + wo] = mag;
             }
     }
     return 0;

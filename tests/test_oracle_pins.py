@@ -789,3 +789,78 @@ def test_conv1d_grad_input_is_the_forward_function_on_flipped_taps_at_stride_one
     wt = np.ascontiguousarray(w.reshape(groups, cog, cig, k).transpose(0, 2, 1, 3)[..., ::-1]).reshape(cin, cog, k)
     via, _ = oracle.conv1d(g, wt, 1, dil * (k - 1) - pad, dil, groups)
     assert np.abs(via - gx).max() < 1e-12
+
+
+# ----------------------------------------------------------------------------- P14
+# pool2d_ex: four-sided padding and the divide-by-real-cells average.
+def test_pool2d_ex_hand_written_case():
+    """3 x 3 plane, 2 x 2 window, stride 1, padding top 1, left 1, bottom 0, right 1."""
+    x = np.array([[[[1, 2, 3], [4, 5, 6], [7, 8, 9]]]], np.float32)
+    y, _ = oracle.pool2d_ex(oracle.OP_ADD, x, 2, 2, 1, 1, (1, 1, 0, 1))
+    assert y[0, 0].tolist() == [[1, 3, 5, 3], [5, 12, 16, 9], [11, 24, 28, 15]]
+    y, _ = oracle.pool2d_ex(oracle.OP_ADD, x, 2, 2, 1, 1, (1, 1, 0, 1), div_valid=True)
+    assert y[0, 0].tolist() == [[1, 1.5, 2.5, 3], [2.5, 3, 4, 4.5], [5.5, 6, 7, 7.5]]
+    y, _ = oracle.pool2d_ex(oracle.OP_MAX, x, 2, 2, 1, 1, (1, 1, 0, 1))
+    assert y[0, 0].tolist() == [[1, 2, 3, 3], [4, 5, 6, 6], [7, 8, 9, 9]]
+    y, _ = oracle.pool2d_ex(oracle.OP_MIN, x, 2, 2, 2, 2, (0, 0, 1, 1))
+    assert y[0, 0].tolist() == [[1, 3], [7, 9]]
+
+
+@pytest.mark.parametrize("kh,kw,sh,sw,pads", [(3, 3, 1, 1, (1, 1, 1, 1)), (3, 3, 2, 2, (0, 1, 2, 0)), (2, 4, 1, 3, (1, 3, 0, 2)),
+                                              (5, 2, 2, 1, (4, 0, 3, 1))])
+def test_pool2d_ex_against_explicit_padding_and_closed_forms(kh, kw, sh, sw, pads):
+    r = _rng(180 + kh + kw)
+    x = r.standard_normal((2, 3, 9, 11), dtype=np.float32)
+    pt, pl, pb, pr = pads
+    for op, fill in ((oracle.OP_ADD, 0.0), (oracle.OP_MAX, -np.inf), (oracle.OP_MIN, np.inf)):
+        y, _ = oracle.pool2d_ex(op, x, kh, kw, sh, sw, pads)
+        xp = np.pad(x.astype(np.float64), ((0, 0), (0, 0), (pt, pb), (pl, pr)), constant_values=fill)
+        red = {oracle.OP_ADD: np.sum, oracle.OP_MAX: np.max, oracle.OP_MIN: np.min}[op]
+        for ho in range(y.shape[2]):
+            for wo in range(y.shape[3]):
+                want = red(xp[:, :, ho * sh:ho * sh + kh, wo * sw:wo * sw + kw], axis=(2, 3))
+                assert np.allclose(y[:, :, ho, wo], want, rtol=0, atol=1e-12)
+    # the number of real cells per window: the plain sum of an all-ones plane; and the mean of a
+    # constant plane over real cells is that constant
+    ones = np.ones((1, 1, 9, 11), np.float32)
+    cnt, _ = oracle.pool2d_ex(oracle.OP_ADD, ones, kh, kw, sh, sw, pads)
+    rows = np.array([min(h * sh - pt + kh, 9) - max(h * sh - pt, 0) for h in range(cnt.shape[2])])
+    cols = np.array([min(w * sw - pl + kw, 11) - max(w * sw - pl, 0) for w in range(cnt.shape[3])])
+    assert np.array_equal(cnt[0, 0], np.outer(rows, cols))
+    mean, _ = oracle.pool2d_ex(oracle.OP_ADD, 3 * ones, kh, kw, sh, sw, pads, div_valid=True)
+    assert np.array_equal(mean, np.full_like(mean, 3.0))
+    ys, _ = oracle.pool2d_ex(oracle.OP_ADD, x, kh, kw, sh, sw, pads)
+    ym, _ = oracle.pool2d_ex(oracle.OP_ADD, x, kh, kw, sh, sw, pads, div_valid=True, scale=2.0)
+    assert np.allclose(ym, 2.0 * ys / cnt, rtol=1e-14, atol=0)
+
+
+def test_pool2d_ex_with_equal_pads_is_pool2d():
+    r = _rng(190)
+    x = r.standard_normal((1, 2, 12, 10), dtype=np.float32)
+    for op in (oracle.OP_ADD, oracle.OP_MAX):
+        a, ma = oracle.pool2d(op, x, 3, 3, 2, 2, 1, 1, 1 / 9)
+        b, mb = oracle.pool2d_ex(op, x, 3, 3, 2, 2, (1, 1, 1, 1), scale=1 / 9)
+        assert np.array_equal(a, b) and np.array_equal(ma, mb)
+
+
+def test_padded_shrinking_window_hand_written_and_closed_forms():
+    """PAD_SHRINK: virtual elements are skipped and add is rescaled by w / (real elements)."""
+    x = np.array([[1, 2, 3, 4, 5]], np.float32)
+    y, _ = oracle.slide1d_padded(oracle.OP_ADD, x, 3, 1, 2, oracle.PAD_SHRINK, 1 / 3)
+    assert np.allclose(y[0], [1.5, 2, 3, 4, 4.5, 5], rtol=1e-15)        # means over 2,3,3,3,2,1 real elements
+    y, _ = oracle.slide1d_padded(oracle.OP_MAX, x, 3, 1, 2, oracle.PAD_SHRINK)
+    assert y[0].tolist() == [2, 3, 4, 5, 5, 5]
+    r = _rng(200)
+    z = r.standard_normal((3, 40), dtype=np.float32)
+    for w, pl, pr in ((5, 2, 2), (7, 6, 0), (4, 0, 3)):
+        a, _ = oracle.slide1d_padded(oracle.OP_ADD, z, w, pl, pr, oracle.PAD_IDENTITY, 1.0)
+        ones, _ = oracle.slide1d_padded(oracle.OP_ADD, np.ones_like(z), w, pl, pr, oracle.PAD_IDENTITY, 1.0)
+        b, _ = oracle.slide1d_padded(oracle.OP_ADD, z, w, pl, pr, oracle.PAD_SHRINK, 1.0 / w)
+        assert np.allclose(b, a / ones, rtol=1e-14, atol=0)
+        c, _ = oracle.slide1d_padded(oracle.OP_ADD, 2 * np.ones_like(z), w, pl, pr, oracle.PAD_SHRINK, 1.0 / w)
+        assert np.allclose(c, 2.0, rtol=1e-15)
+        m0, _ = oracle.slide1d_padded(oracle.OP_MIN, z, w, pl, pr, oracle.PAD_IDENTITY)
+        m4, _ = oracle.slide1d_padded(oracle.OP_MIN, z, w, pl, pr, oracle.PAD_SHRINK)
+        assert np.array_equal(m0, m4)
+    with pytest.raises(ValueError):
+        oracle.slide1d_padded(oracle.OP_ADD, z, 3, 3, 0, oracle.PAD_SHRINK)
