@@ -49,7 +49,10 @@ typedef enum {
     SWS_PAD_IDENTITY = 0,      /* the identity of the operator: 0 for ADD, -inf for MAX, +inf for MIN */
     SWS_PAD_MIRROR = 1,        /* x[-i] = x[i], x[len-1+i] = x[len-1-i] (end elements not repeated) */
     SWS_PAD_PERIODIC = 2,      /* x[-i] = x[len-i], x[len-1+i] = x[i-1] */
-    SWS_PAD_EDGE = 3           /* x[-i] = x[0], x[len-1+i] = x[len-1] */
+    SWS_PAD_EDGE = 3,          /* x[-i] = x[0], x[len-1+i] = x[len-1] */
+    SWS_PAD_SHRINK = 4         /* the window shrinks at the ends: virtual elements are skipped and an ADD
+                                  result is multiplied by w / n, n = real elements in the window, so that
+                                  scale = 1/w gives the mean over real elements (pads must be < w) */
 } sws_pad_mode;
 
 /* Sliding window sum, Section 2.2 Eq. 3, applied to `rows` independent sequences:
@@ -73,7 +76,8 @@ sws_status sws_slide1d(sws_op op, const float *x, float *y, int64_t rows, int64_
  * input ("same" pooling).  scale multiplies ADD results, padding included.
  *   x : device, rows*len floats     y : device, rows*(len+pad_left+pad_right-w+1) floats
  * Errors: as sws_slide1d, and INVALID_ARG if len < 1, a pad is negative, w exceeds the extended
- * row, the mode is unknown, a MIRROR pad exceeds len-1 or a PERIODIC pad exceeds len. */
+ * row, the mode is unknown, a MIRROR pad exceeds len-1, a PERIODIC pad exceeds len or a SHRINK
+ * pad is not smaller than w. */
 sws_status sws_slide1d_padded(sws_op op, const float *x, float *y, int64_t rows, int64_t len,
                               int32_t w, int32_t pad_left, int32_t pad_right, sws_pad_mode mode,
                               float scale, void *stream);
@@ -125,6 +129,30 @@ sws_status sws_slide1d_pair(const float *u, const float *v, float *yu, float *yv
 sws_status sws_pool2d(sws_op op, const float *x, float *y, int64_t N, int64_t C, int64_t H,
                       int64_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
                       int32_t ph, int32_t pw, float scale, void *stream);
+
+/* What an ADD result of sws_pool2d_ex is divided by. */
+typedef enum {
+    SWS_DIV_SCALE = 0,         /* nothing: y = scale * sum (scale = 1/(kh*kw): the average that counts padding) */
+    SWS_DIV_REAL_CELLS = 1     /* the number of window cells inside the plane: y = scale * sum / n
+                                  (scale = 1: the average that does not count padding) */
+} sws_divisor;
+
+/* sws_pool2d with separate padding on the four sides and a choice of averaging rule (boundary
+ * handling beyond the symmetric padding of sws_pool2d; Section 3 leaves boundary conditions to
+ * the application):
+ *
+ *   y[n,c,ho,wo] = f * (+)_{a<kh} (+)_{b<kw} x[n,c, ho*sh - pad_top + a, wo*sw - pad_left + b]
+ *   Ho = (H + pad_top + pad_bottom - kh)/sh + 1,  Wo = (W + pad_left + pad_right - kw)/sw + 1
+ *
+ * Cells outside the plane hold the identity of op.  f = scale, or scale / n with n the number of
+ * window cells inside the plane (divisor; ADD only, MAX / MIN ignore both).
+ *   x : device, N*C*H*W floats          y : device, N*C*Ho*Wo floats
+ * Errors: as sws_pool2d; every pad must be smaller than the kernel extent on its axis (each
+ * window then holds a real cell); H, W >= 1; unknown divisor. */
+sws_status sws_pool2d_ex(sws_op op, const float *x, float *y, int64_t N, int64_t C, int64_t H,
+                         int64_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                         int32_t pad_top, int32_t pad_left, int32_t pad_bottom, int32_t pad_right,
+                         sws_divisor divisor, float scale, void *stream);
 
 /* 1-D convolution as a sliding dot product (Section 2.5; Eq. 4 per output), in the DNN
  * sense: cross-correlation, taps not flipped, zero padding, no bias.

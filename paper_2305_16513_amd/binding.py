@@ -19,7 +19,7 @@ _lib = None
 
 _i64, _i32, _f32, _vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
 
-EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_conv1d", "sws_conv1d_grad_input", "sws_conv1d_grad_weight", "sws_conv2d", "sws_copy", "sws_out_len",
+EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_pool2d_ex", "sws_conv1d", "sws_conv1d_grad_input", "sws_conv1d_grad_weight", "sws_conv2d", "sws_copy", "sws_out_len",
            "sws_status_string", "sws_set_option", "sws_version")
 
 
@@ -48,6 +48,9 @@ def lib():
         L.sws_pool2d.restype = ctypes.c_int
         L.sws_pool2d.argtypes = [ctypes.c_int, _vp, _vp, _i64, _i64, _i64, _i64,
                                  _i32, _i32, _i32, _i32, _i32, _i32, _f32, _vp]
+        L.sws_pool2d_ex.restype = ctypes.c_int
+        L.sws_pool2d_ex.argtypes = [ctypes.c_int, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32,
+                                    _i32, _i32, _i32, _i32, ctypes.c_int, _f32, _vp]
         L.sws_conv1d.restype = ctypes.c_int
         L.sws_conv1d.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _vp]
         for f in (L.sws_conv1d_grad_input, L.sws_conv1d_grad_weight):
@@ -155,7 +158,7 @@ def sws_slide1d_16(op, x, w, scale=1.0, y=None, stream=None):
     return y
 
 
-SWS_PAD_IDENTITY, SWS_PAD_MIRROR, SWS_PAD_PERIODIC, SWS_PAD_EDGE = 0, 1, 2, 3
+SWS_PAD_IDENTITY, SWS_PAD_MIRROR, SWS_PAD_PERIODIC, SWS_PAD_EDGE, SWS_PAD_SHRINK = 0, 1, 2, 3, 4
 
 
 def sws_slide1d_padded(op, x, w, pad_left, pad_right, mode, scale=1.0, y=None, stream=None):
@@ -200,6 +203,23 @@ def sws_pool2d(op, x, kh, kw, sh=1, sw=1, ph=0, pw=0, scale=1.0, y=None, stream=
     y = _out(y, (n, c, ho, wo), x)
     _check(lib().sws_pool2d(op, x.data_ptr(), y.data_ptr(), n, c, h, wd, kh, kw, sh, sw, ph, pw, scale,
                             _stream(stream)), "sws_pool2d")
+    return y
+
+
+SWS_DIV_SCALE, SWS_DIV_REAL_CELLS = 0, 1
+
+
+def sws_pool2d_ex(op, x, kh, kw, sh=1, sw=1, pads=(0, 0, 0, 0), divisor=SWS_DIV_SCALE, scale=1.0, y=None, stream=None):
+    """x [N, C, H, W], pads = (top, left, bottom, right) -> y [N, C, Ho, Wo]."""
+    _dev(x, "x")
+    n, c, h, wd = x.shape
+    pt, pl, pb, pr = pads
+    ho, wo = (h + pt + pb - kh) // sh + 1, (wd + pl + pr - kw) // sw + 1
+    if ho < 1 or wo < 1 or min(pads) < 0:
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_pool2d_ex")
+    y = _out(y, (n, c, ho, wo), x)
+    _check(lib().sws_pool2d_ex(op, x.data_ptr(), y.data_ptr(), n, c, h, wd, kh, kw, sh, sw, pt, pl, pb, pr, divisor,
+                               scale, _stream(stream)), "sws_pool2d_ex")
     return y
 
 

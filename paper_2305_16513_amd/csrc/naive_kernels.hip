@@ -25,11 +25,13 @@ __global__ __launch_bounds__(kThreads) void slide_naive_kernel(const float *__re
         const int i = (int)(o - r * lo);
         const float *xr = x + r * (int64_t)len;
         float acc = O::id();
+        int real = 0;                                // elements that are not identity padding
         for (int j = 0; j < w; ++j) {
             const int src = pad_src(i + j, len, pad_left, pad_mode);
             acc = O::f(acc, src >= 0 ? xr[src] : O::id());
+            real += src >= 0;
         }
-        if (OP == SWS_OP_ADD) acc *= scale;
+        if (OP == SWS_OP_ADD) acc *= (pad_mode == SWS_PAD_SHRINK && real > 0) ? scale * (float)w / (float)real : scale;
         y[o] = acc;
     }
 }
@@ -40,7 +42,7 @@ __global__ __launch_bounds__(kThreads) void pool2d_naive_kernel(const float *__r
                                                                 float *__restrict__ y, int64_t planes,
                                                                 int H, int W, int Ho, int Wo, int kh,
                                                                 int kw, int sh, int sw, int ph, int pw,
-                                                                float scale)
+                                                                float scale, int div_valid)
 {
     using O = Op<OP>;
     const int64_t total = planes * (int64_t)Ho * Wo;
@@ -51,6 +53,7 @@ __global__ __launch_bounds__(kThreads) void pool2d_naive_kernel(const float *__r
         const int64_t p = o / ((int64_t)Wo * Ho);
         const float *xp = x + p * (int64_t)H * W;
         float acc = O::id();
+        int cells = 0;                               // window cells inside the plane
         for (int b = 0; b < kw; ++b) {
             const int c = wo * sw - pw + b;
             if (c < 0 || c >= W) continue;
@@ -59,10 +62,11 @@ __global__ __launch_bounds__(kThreads) void pool2d_naive_kernel(const float *__r
                 const int h = ho * sh - ph + a;
                 if (h < 0 || h >= H) continue;
                 col = O::f(col, xp[(int64_t)h * W + c]);
+                ++cells;
             }
             acc = O::f(acc, col);
         }
-        if (OP == SWS_OP_ADD) acc *= scale;
+        if (OP == SWS_OP_ADD) acc *= div_valid ? scale / (float)cells : scale;
         y[o] = acc;
     }
 }
@@ -159,12 +163,12 @@ hipError_t launch_slide1d_naive(int op, const float *x, float *y, int64_t rows, 
 
 hipError_t launch_pool2d_naive(int op, const float *x, float *y, int64_t planes, int64_t H, int64_t W,
                                int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
-                               int32_t ph, int32_t pw, float scale, hipStream_t s)
+                               int32_t ph, int32_t pw, float scale, int div_valid, hipStream_t s)
 {
     const int grid = grid_for(planes * Ho * Wo);
 #define SWS_LAUNCH_POOL(OPV)                                                                             \
     hipLaunchKernelGGL(pool2d_naive_kernel<OPV>, dim3(grid), dim3(kThreads), 0, s, x, y, planes, (int)H, \
-                       (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw, scale)
+                       (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw, scale, div_valid)
     switch (op) {
     case SWS_OP_ADD: SWS_LAUNCH_POOL(SWS_OP_ADD); break;
     case SWS_OP_MAX: SWS_LAUNCH_POOL(SWS_OP_MAX); break;

@@ -46,7 +46,8 @@ __global__ __launch_bounds__(kThreads) void pool2d_band_kernel(
     constexpr int NG = (OFF + NC + 3) / 4;           // aligned 4-column groups per input row
     extern __shared__ __attribute__((aligned(16))) float lds_all[];
 
-    // flag bits: 2 = XCD-contiguous placement of workgroups (default: launch order), 4 = plain stores
+    // flag bits: 2 = XCD-contiguous placement of workgroups (default: launch order), 4 = plain stores,
+    // 8 = ADD results are divided by the number of window cells inside the plane
     const int64_t wg = (flags & 2) ? xcd_unit((n_units + kWaves - 1) / kWaves) : (int64_t)blockIdx.x;
     if (wg < 0) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -132,7 +133,17 @@ __global__ __launch_bounds__(kThreads) void pool2d_band_kernel(
                 float acc = v[e * SW];
 #pragma unroll
                 for (int b = 1; b < KW; ++b) acc = O::f(acc, v[e * SW + b]);
-                o[e] = (OP == SWS_OP_ADD) ? acc * scale : acc;
+                if (OP == SWS_OP_ADD) {
+                    float sc = scale;
+                    if (flags & 8) {                 // real cells of this window: rows x columns inside the plane
+                        const int h0 = hin0 + ro * SH, c0 = (4 * cg + e) * SW - PW;
+                        const int nr = (h0 + KH < H ? h0 + KH : H) - (h0 > 0 ? h0 : 0);
+                        const int nc = (c0 + KW < W ? c0 + KW : W) - (c0 > 0 ? c0 : 0);
+                        sc = scale / (float)(nr * nc);
+                    }
+                    acc *= sc;
+                }
+                o[e] = acc;
             }
             float *dst = yp + (int64_t)(ho + ro) * Wo + 4 * cg;
             if (4 * cg + 4 <= Wo) {
@@ -175,13 +186,13 @@ BandPlan plan_bands(int W, int Ho, int Wo, int KH, int SH, int R)
 
 template <int OP, int KH, int KW, int SH, int SW, int PW>
 hipError_t launch_band(const float *x, float *y, int64_t planes, int H, int W, int Ho, int Wo, int ph, float scale,
-                       hipStream_t s, bool *taken)
+                       int div_valid, hipStream_t s, bool *taken)
 {
     const BandPlan p = plan_bands(W, Ho, Wo, KH, SH, RowsPerItem<SH>::value);
     *taken = p.ok;
     if (!p.ok) return hipSuccess;
     const int64_t n_units = planes * p.bands;
-    const int flags = g_opt.pool2d_variant;
+    const int flags = (g_opt.pool2d_variant & 6) | (div_valid ? 8 : 0);
     const int64_t n_wg = (n_units + kWaves - 1) / kWaves;
     const int64_t grid = (flags & 2) ? xcd_grid(n_wg) : n_wg;
     if (grid > 2147483647LL) { *taken = false; return hipSuccess; }
@@ -193,11 +204,11 @@ hipError_t launch_band(const float *x, float *y, int64_t planes, int H, int W, i
 
 template <int OP>
 hipError_t dispatch_band(const float *x, float *y, int64_t planes, int H, int W, int Ho, int Wo, int kh, int kw,
-                         int sh, int sw, int ph, int pw, float scale, hipStream_t s, bool *taken)
+                         int sh, int sw, int ph, int pw, float scale, int div_valid, hipStream_t s, bool *taken)
 {
 #define SWS_BAND(KH, KW, SH, SW, PW)                                                                  \
     if (kh == KH && kw == KW && sh == SH && sw == SW && pw == PW)                                      \
-        return launch_band<OP, KH, KW, SH, SW, PW>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken)
+        return launch_band<OP, KH, KW, SH, SW, PW>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken)
     SWS_BAND(3, 3, 1, 1, 1);
     SWS_BAND(3, 3, 2, 2, 1);
     SWS_BAND(3, 3, 1, 1, 0);
@@ -218,28 +229,30 @@ hipError_t dispatch_band(const float *x, float *y, int64_t planes, int H, int W,
 
 hipError_t launch_pool2d(int op, const float *x, float *y, int64_t planes, int64_t H, int64_t W, int64_t Ho,
                          int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
-                         float scale, hipStream_t s)
+                         float scale, int div_valid, hipStream_t s)
 {
+    // ph / pw are the top / left padding; the bottom / right padding is implied by Ho / Wo (cells
+    // beyond the plane hold the identity whichever side they are on).
     if (g_opt.pool2d_variant != 1) {
         bool taken = false;
         hipError_t e;
         switch (op) {
         case SWS_OP_ADD:
             e = dispatch_band<SWS_OP_ADD>(x, y, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw,
-                                          scale, s, &taken);
+                                          scale, div_valid, s, &taken);
             break;
         case SWS_OP_MAX:
             e = dispatch_band<SWS_OP_MAX>(x, y, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw,
-                                          scale, s, &taken);
+                                          scale, div_valid, s, &taken);
             break;
         default:
             e = dispatch_band<SWS_OP_MIN>(x, y, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw,
-                                          scale, s, &taken);
+                                          scale, div_valid, s, &taken);
             break;
         }
         if (taken) return e;
     }
-    return launch_pool2d_naive(op, x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, s);
+    return launch_pool2d_naive(op, x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, div_valid, s);
 }
 
 }  // namespace sws

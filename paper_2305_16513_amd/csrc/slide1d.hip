@@ -335,7 +335,18 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
             v4f o;
             o.x = O::f(s4v.x, pn.x); o.y = O::f(s4v.y, pn.y); o.z = O::f(s4v.z, pn.z); o.w = O::f(s4v.w, pn.w);
             if (MODE != 2) {
-                if (OP == SWS_OP_ADD) o *= scale;
+                if (PADDED && OP == SWS_OP_ADD && pad_mode == SWS_PAD_SHRINK) {
+                    // the window shrinks at the ends of the row: rescale by w / (real elements in it)
+                    float ov[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const int e = t0 + q + c;    // first element of the window, in the extended row
+                        const int hi = e + S + 1 < pad_left + len ? e + S + 1 : pad_left + len;
+                        const int n = hi - (e > pad_left ? e : pad_left);
+                        ov[c] *= scale * (float)(S + 1) / (float)(n > 0 ? n : 1);
+                    }
+                    o = (v4f){ov[0], ov[1], ov[2], ov[3]};
+                } else if (OP == SWS_OP_ADD) o *= scale;
             } else {
                 if (chain_acc) {                     // earlier links cover older elements: they go on the left
                     if (q >= qlo && q + 4 <= lim) {

@@ -102,7 +102,8 @@ sws_status sws_slide1d_padded(sws_op op, const float *x, float *y, int64_t rows,
                               int32_t pad_left, int32_t pad_right, sws_pad_mode mode, float scale, void *stream)
 {
     if (!valid_op((int)op) || rows < 0 || len < 1 || w < 1 || pad_left < 0 || pad_right < 0) return SWS_ERR_INVALID_ARG;
-    if ((int)mode < SWS_PAD_IDENTITY || (int)mode > SWS_PAD_EDGE) return SWS_ERR_INVALID_ARG;
+    if ((int)mode < SWS_PAD_IDENTITY || (int)mode > SWS_PAD_SHRINK) return SWS_ERR_INVALID_ARG;
+    if (mode == SWS_PAD_SHRINK && (pad_left >= w || pad_right >= w)) return SWS_ERR_INVALID_ARG;
     const int64_t lv = len + pad_left + pad_right;
     if (lv > kMaxDim || (int64_t)w > lv) return SWS_ERR_INVALID_ARG;
     if (mode == SWS_PAD_MIRROR && (pad_left > len - 1 || pad_right > len - 1)) return SWS_ERR_INVALID_ARG;
@@ -143,8 +144,31 @@ sws_status sws_pool2d(sws_op op, const float *x, float *y, int64_t N, int64_t C,
     if (H * W > kMaxDim) return SWS_ERR_UNSUPPORTED;
     if (planes == 0) return SWS_OK;
     if (!x || !y) return SWS_ERR_INVALID_ARG;
-    return from_hip(sws::launch_pool2d((int)op, x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale,
+    return from_hip(sws::launch_pool2d((int)op, x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, 0,
                                        (hipStream_t)stream));
+}
+
+sws_status sws_pool2d_ex(sws_op op, const float *x, float *y, int64_t N, int64_t C, int64_t H, int64_t W,
+                         int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t pad_top, int32_t pad_left,
+                         int32_t pad_bottom, int32_t pad_right, sws_divisor divisor, float scale, void *stream)
+{
+    if (!valid_op((int)op) || N < 0 || C < 0 || H < 1 || W < 1) return SWS_ERR_INVALID_ARG;
+    if (kh < 1 || kw < 1 || sh < 1 || sw < 1) return SWS_ERR_INVALID_ARG;
+    if (pad_top < 0 || pad_left < 0 || pad_bottom < 0 || pad_right < 0) return SWS_ERR_INVALID_ARG;
+    if (pad_top >= kh || pad_bottom >= kh || pad_left >= kw || pad_right >= kw) return SWS_ERR_INVALID_ARG;
+    if (divisor != SWS_DIV_SCALE && divisor != SWS_DIV_REAL_CELLS) return SWS_ERR_INVALID_ARG;
+    if (H > kMaxDim || W > kMaxDim) return SWS_ERR_INVALID_ARG;
+    const int64_t He = H + pad_top + pad_bottom, We = W + pad_left + pad_right;
+    if (kh > He || kw > We) return SWS_ERR_INVALID_ARG;
+    const int64_t Ho = (He - kh) / sh + 1, Wo = (We - kw) / sw + 1;
+    int64_t planes, n_in, n_out;
+    if (!mul3(N, C, 1, &planes) || !mul3(planes, H, W, &n_in) || !mul3(planes, Ho, Wo, &n_out))
+        return SWS_ERR_INVALID_ARG;
+    if (H * W > kMaxDim) return SWS_ERR_UNSUPPORTED;
+    if (planes == 0) return SWS_OK;
+    if (!x || !y) return SWS_ERR_INVALID_ARG;
+    return from_hip(sws::launch_pool2d((int)op, x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, pad_top, pad_left, scale,
+                                       divisor == SWS_DIV_REAL_CELLS ? 1 : 0, (hipStream_t)stream));
 }
 
 sws_status sws_conv1d(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin, int64_t L,

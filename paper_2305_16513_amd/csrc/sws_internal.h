@@ -45,12 +45,13 @@ template <> struct Op<SWS_OP_MIN> {
 // Boundary conditions of a row extended by pad_left virtual elements in front (and more behind):
 // the physical index that virtual element e stands for, or -1 for the operator's identity.
 // mode: SWS_PAD_IDENTITY, SWS_PAD_MIRROR (x[-i] = x[i]), SWS_PAD_PERIODIC (x[-i] = x[len-i]),
-// SWS_PAD_EDGE (the end element repeated).  The caller keeps e inside the extended row.
+// SWS_PAD_EDGE (the end element repeated), SWS_PAD_SHRINK (identity; the caller rescales ADD results).
+// The caller keeps e inside the extended row.
 __device__ __forceinline__ int pad_src(int e, int len, int pad_left, int mode)
 {
     const int p = e - pad_left;
     if (p >= 0 && p < len) return p;
-    if (mode == SWS_PAD_IDENTITY) return -1;
+    if (mode == SWS_PAD_IDENTITY || mode == SWS_PAD_SHRINK) return -1;
     if (mode == SWS_PAD_MIRROR) return p < 0 ? -p : 2 * (len - 1) - p;
     if (mode == SWS_PAD_PERIODIC) return p < 0 ? p + len : p - len;
     return p < 0 ? 0 : len - 1;
@@ -80,7 +81,7 @@ hipError_t launch_slide1d_generic(int op, const float *x, float *y, int64_t rows
                                   hipStream_t s);
 hipError_t launch_pool2d(int op, const float *x, float *y, int64_t planes, int64_t H, int64_t W,
                          int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
-                         int32_t ph, int32_t pw, float scale, hipStream_t s);
+                         int32_t ph, int32_t pw, float scale, int div_valid, hipStream_t s);
 hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin, int64_t L,
                          int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad,
                          int32_t dilation, int32_t groups, hipStream_t s, int wadj = 0, bool *taken = nullptr);
@@ -106,7 +107,7 @@ hipError_t launch_slide1d_naive(int op, const float *x, float *y, int64_t rows, 
                                 int32_t pad_left, int32_t pad_right, int pad_mode, float scale, hipStream_t s);
 hipError_t launch_pool2d_naive(int op, const float *x, float *y, int64_t planes, int64_t H, int64_t W,
                                int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
-                               int32_t ph, int32_t pw, float scale, hipStream_t s);
+                               int32_t ph, int32_t pw, float scale, int div_valid, hipStream_t s);
 hipError_t launch_conv1d_naive(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin,
                                int64_t L, int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad,
                                int32_t dilation, int32_t groups, hipStream_t s);

@@ -73,7 +73,8 @@ def test_slide1d_padded_argument_checks(L):
     f = L.sws_slide1d_padded
     assert f(0, one, one, 0, 100, 3, 1, 1, 0, 1.0, nul) == 0               # no rows: nothing to do
     assert f(0, one, one, 1, 100, 3, -1, 1, 0, 1.0, nul) == 1              # negative pad
-    assert f(0, one, one, 1, 100, 3, 1, 1, 4, 1.0, nul) == 1               # unknown mode
+    assert f(0, one, one, 1, 100, 3, 1, 1, 5, 1.0, nul) == 1               # unknown mode
+    assert f(0, one, one, 1, 100, 3, 3, 1, 4, 1.0, nul) == 1               # shrinking window: pad not below w
     assert f(0, one, one, 1, 100, 103, 1, 1, 0, 1.0, nul) == 1             # w longer than the extended row
     assert f(0, one, one, 1, 100, 3, 100, 0, 1, 1.0, nul) == 1             # mirror pad reaches past the row
     assert f(0, one, one, 1, 100, 3, 0, 101, 2, 1.0, nul) == 1             # periodic pad longer than the row
@@ -151,3 +152,29 @@ def test_binding_refuses_cpu_tensors():
     from paper_2305_16513_amd import binding
     with pytest.raises(TypeError):
         binding.sws_slide1d(0, torch.zeros(8), 3)
+
+
+def test_new_entry_points_argument_checks(L):
+    """sws_slide1d_16, sws_pool2d_ex and the conv1d adjoints reject bad arguments before any launch."""
+    one, nul = ctypes.c_void_p(16), ctypes.c_void_p(0)
+    i64, i32, f32 = ctypes.c_int64, ctypes.c_int32, ctypes.c_float
+    L.sws_slide1d_16.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, i64, i64, i32, f32, ctypes.c_void_p]
+    assert L.sws_slide1d_16(0, 1, one, one, 0, 100, 3, 1.0, nul) == 0      # no rows
+    assert L.sws_slide1d_16(0, 0, one, one, 1, 100, 3, 1.0, nul) == 1      # fp32 is not a 16-bit type
+    assert L.sws_slide1d_16(0, 2, one, one, 1, 100, 101, 1.0, nul) == 1    # window longer than the row
+    assert L.sws_slide1d_16(0, 2, nul, one, 1, 100, 3, 1.0, nul) == 1
+    L.sws_pool2d_ex.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, i64, i64, i64, i64, i32, i32, i32, i32,
+                                i32, i32, i32, i32, ctypes.c_int, f32, ctypes.c_void_p]
+    pe = lambda **kw: L.sws_pool2d_ex(*[kw.get(n, v) for n, v in zip(
+        ("op", "x", "y", "N", "C", "H", "W", "kh", "kw", "sh", "sw", "pt", "pl", "pb", "pr", "div", "scale", "s"),
+        (0, one, one, 1, 3, 8, 8, 3, 3, 1, 1, 1, 0, 2, 1, 0, 1.0, nul))])
+    assert pe(N=0) == 0
+    assert pe(pt=3) == 1 and pe(pb=3) == 1 and pe(pl=3) == 1 and pe(pr=-1) == 1
+    assert pe(div=2) == 1 and pe(op=4) == 1 and pe(y=nul) == 1 and pe(H=0) == 1
+    for f in (L.sws_conv1d_grad_input, L.sws_conv1d_grad_weight):
+        f.argtypes = [ctypes.c_void_p] * 3 + [i64, i64, i64, i64, i32, i32, i32, i32, i32, ctypes.c_void_p]
+        g = lambda **kw: f(*[kw.get(n, v) for n, v in zip(
+            ("a", "b", "c", "B", "Cin", "L", "Cout", "k", "stride", "pad", "dil", "groups", "s"),
+            (one, one, one, 1, 4, 32, 6, 3, 1, 0, 1, 1, nul))])
+        assert g(groups=3) == 1 and g(k=0) == 1 and g(k=40) == 1 and g(stride=0) == 1 and g(c=nul) == 1
+    assert L.sws_conv1d_grad_input(one, one, one, 0, 4, 32, 6, 3, 1, 0, 1, 1, nul) == 0

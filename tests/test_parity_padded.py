@@ -88,3 +88,22 @@ def test_same_size_pooling_on_cfg2_shape(B):
             assert_within_tol(to_host(y).reshape(ref.shape), ref, mag, "cfg2 same avg mode %d" % mode)
         else:
             assert_bit_exact(to_host(y).reshape(ref.shape), ref, "cfg2 same max mode %d" % mode)
+
+
+@pytest.mark.parametrize("op", [0, 1, 2])
+@pytest.mark.parametrize("w,pl,pr", [(1, 0, 0), (2, 1, 0), (3, 1, 1), (5, 4, 2), (16, 15, 0), (31, 15, 15), (64, 0, 63),
+                                     (255, 127, 127), (961, 480, 480), (1200, 600, 599)])
+@pytest.mark.parametrize("length", [700, 3001])
+def test_shrinking_window_mode(B, op, w, pl, pr, length):
+    """SWS_PAD_SHRINK: average over the real elements of a window that hangs over an end of the row."""
+    r = _rng(5000 + op * 100 + w + length)
+    x = (r.random((3, length), dtype=np.float32) * 2 - 1).astype(np.float32)
+    _check(B, op, x, w, pl, pr, 4, "shrink op=%d w=%d pads=(%d,%d) len=%d" % (op, w, pl, pr, length))
+
+
+def test_shrinking_window_constant_row_and_argument_checks(B):
+    x = np.full((2, 500), 3.0, np.float32)
+    y = to_host(B.sws_slide1d_padded(0, to_gpu(x), 9, 4, 4, B.SWS_PAD_SHRINK, 1.0 / 9))
+    assert np.abs(y - 3.0).max() < 1e-5
+    with pytest.raises(B.SwsError):
+        B.sws_slide1d_padded(0, to_gpu(x), 9, 9, 0, B.SWS_PAD_SHRINK, 1.0)

@@ -112,3 +112,41 @@ def test_cfg3_full_size_sampled_planes(B, stride):
         if stride == 2:
             y1 = B.sws_pool2d(OPS[op], xg, 3, 3, 1, 1, 1, 1, 1.0 / 9)
             assert torch.equal(yg, y1[:, :, ::2, ::2])
+
+
+EX_GEOMS = [  # kh, kw, sh, sw, (top, left, bottom, right)
+    (3, 3, 1, 1, (1, 1, 1, 1)), (3, 3, 2, 2, (1, 1, 0, 0)), (3, 3, 2, 2, (0, 0, 1, 1)), (2, 2, 2, 2, (0, 0, 1, 1)),
+    (3, 3, 1, 1, (2, 1, 0, 2)), (5, 5, 1, 1, (4, 2, 1, 3)), (7, 7, 1, 1, (0, 3, 6, 3)), (3, 3, 2, 2, (2, 1, 2, 2)),
+    (4, 3, 2, 1, (1, 2, 3, 0)), (2, 5, 1, 3, (1, 4, 0, 2))]
+
+
+@pytest.mark.parametrize("divisor", [0, 1])
+@pytest.mark.parametrize("op", [0, 1, 2])
+@pytest.mark.parametrize("geom", EX_GEOMS)
+@pytest.mark.parametrize("shape", [(3, 5, 37, 41), (2, 3, 112, 112), (1, 2, 8, 300)])
+def test_four_sided_padding_and_real_cell_average(B, divisor, op, geom, shape):
+    """sws_pool2d_ex: separate padding per side; ADD divided by the window's real cells."""
+    kh, kw, sh, sw, pads = geom
+    if divisor and op:
+        pytest.skip("the divisor only applies to add")
+    r = np.random.Generator(np.random.PCG64(kh * 100 + kw * 10 + sh + sum(pads) + shape[2]))
+    x = r.standard_normal(shape, dtype=np.float32)
+    scale = 1.0 if divisor else 1.0 / (kh * kw)
+    y = to_host(B.sws_pool2d_ex(op, to_gpu(x), kh, kw, sh, sw, pads, divisor, scale))
+    ref, mag = oracle.pool2d_ex(op, x, kh, kw, sh, sw, pads, bool(divisor), scale)
+    if op == 0:
+        assert_within_tol(y, ref, mag, "pool2d_ex %s div=%d" % (geom, divisor))
+    else:
+        assert_bit_exact(y, ref, "pool2d_ex %s op=%d" % (geom, op))
+
+
+def test_pool2d_ex_equal_pads_match_pool2d_and_argument_checks(B):
+    r = np.random.Generator(np.random.PCG64(77))
+    x = to_gpu(r.standard_normal((2, 4, 56, 56), dtype=np.float32))
+    a = to_host(B.sws_pool2d(0, x, 3, 3, 2, 2, 1, 1, 1 / 9))
+    b = to_host(B.sws_pool2d_ex(0, x, 3, 3, 2, 2, (1, 1, 1, 1), B.SWS_DIV_SCALE, 1 / 9))
+    assert np.array_equal(a, b)
+    with pytest.raises(B.SwsError):
+        B.sws_pool2d_ex(0, x, 3, 3, 1, 1, (3, 0, 0, 0))
+    with pytest.raises(B.SwsError):
+        B.sws_pool2d_ex(0, x, 3, 3, 1, 1, (0, 0, 0, 0), 5)
