@@ -17,6 +17,8 @@ from .ref import (  # noqa: F401
     conv1d_grad_input,
     conv1d_grad_weight,
     conv2d,
+    conv2d_grad_input,
+    conv2d_grad_weight,
     pool2d,
     pool2d_ex,
     round16,

@@ -56,6 +56,9 @@ def _load():
         for f in (lib.sws_ref_conv1d_grad_input, lib.sws_ref_conv1d_grad_weight):
             f.restype = ctypes.c_int
             f.argtypes = [_fp, _fp, _dp, _dp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32]
+        for f in (lib.sws_ref_conv2d_grad_input, lib.sws_ref_conv2d_grad_weight):
+            f.restype = ctypes.c_int
+            f.argtypes = [_fp, _fp, _dp, _dp, _i64, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _i32]
         lib.sws_ref_round16.restype = ctypes.c_int
         lib.sws_ref_round16.argtypes = [_dp, _dp, _i64, ctypes.c_int]
         lib.sws_ref_conv1d.restype = ctypes.c_int
@@ -269,3 +272,38 @@ def pool2d_ex(op, x, kh, kw, sh=1, sw=1, pads=(0, 0, 0, 0), div_valid=False, sca
     if rc:
         raise ValueError("sws_ref_pool2d_ex rejected its arguments")
     return y, s
+
+
+def conv2d_grad_input(gy, wgt, h, wd, sh=1, sw=1, ph=0, pw=0):
+    """gy: [N, Cout, Ho, Wo], wgt: [Cout, Cin, kh, kw] float32, (h, wd) = the forward input's plane
+    -> (gx, abs_sum) [N, Cin, H, W] float64 (serial: small cases only)."""
+    gy = _f32(gy)
+    wgt = _f32(wgt)
+    n, cout, ho, wo = gy.shape
+    cout2, cin, kh, kw = wgt.shape
+    if cout2 != cout or ho != (h + 2 * ph - kh) // sh + 1 or wo != (wd + 2 * pw - kw) // sw + 1:
+        raise ValueError("gy does not have the forward output's shape")
+    gx = np.empty((n, cin, h, wd), np.float64)
+    s = np.empty((n, cin, h, wd), np.float64)
+    rc = _load().sws_ref_conv2d_grad_input(_ptr_f(gy), _ptr_f(wgt), _ptr_d(gx), _ptr_d(s), n, cin, h, wd, cout,
+                                           kh, kw, sh, sw, ph, pw)
+    if rc:
+        raise ValueError("sws_ref_conv2d_grad_input rejected its arguments")
+    return gx, s
+
+
+def conv2d_grad_weight(x, gy, kh, kw, sh=1, sw=1, ph=0, pw=0):
+    """x: [N, Cin, H, W], gy: [N, Cout, Ho, Wo] float32 -> (gw, abs_sum) [Cout, Cin, kh, kw] float64."""
+    x = _f32(x)
+    gy = _f32(gy)
+    n, cin, h, wd = x.shape
+    n2, cout, ho, wo = gy.shape
+    if n2 != n or ho != (h + 2 * ph - kh) // sh + 1 or wo != (wd + 2 * pw - kw) // sw + 1:
+        raise ValueError("gy does not have the forward output's shape")
+    gw = np.empty((cout, cin, kh, kw), np.float64)
+    s = np.empty((cout, cin, kh, kw), np.float64)
+    rc = _load().sws_ref_conv2d_grad_weight(_ptr_f(x), _ptr_f(gy), _ptr_d(gw), _ptr_d(s), n, cin, h, wd, cout,
+                                            kh, kw, sh, sw, ph, pw)
+    if rc:
+        raise ValueError("sws_ref_conv2d_grad_weight rejected its arguments")
+    return gw, s

@@ -34,6 +34,7 @@
  *                    the forward sum's terms: every term wgt*x of output (b,co,i) sends
  *                    wgt*gy to gx at x's index and x*gy to gw at wgt's index.  The GPU
  *                    gathers instead (flipped taps, swapped channels; a reduction).
+ *   sws_ref_conv2d_grad_input / _grad_weight  the same two adjoints for sws_ref_conv2d.
  *   sws_ref_round16  the value of the bf16 / fp16 number nearest to a double (ties to the even
  *                    significand, overflow to infinity): how a result computed on 16-bit
  *                    storage (the quantised inputs the paper's introduction mentions) is
@@ -476,4 +477,58 @@ int sws_ref_pool2d_ex(int op, const float *x, double *y, double *abs_sum,
             }
     }
     return 0;
+}
+
+/* Adjoints of sws_ref_conv2d in scatter form: every forward term wgt[co,ci,a,b] * x[n,ci,h,c] of
+ * output (n,co,ho,wo), h = ho*sh - ph + a, c = wo*sw - pw + b, sends wgt * gy to gx[n,ci,h,c]
+ * (which = 0) or x * gy to gw[co,ci,a,b] (which = 1).  `other` is wgt for which = 0 and x for
+ * which = 1; out / abs_sum have the shape of x resp. wgt. */
+static int conv2d_adjoint(int which, const float *other, const float *gy, double *out, double *abs_sum,
+                          int64_t N, int64_t Cin, int64_t H, int64_t W, int64_t Cout,
+                          int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw)
+{
+    if (N < 0 || Cin < 1 || H < 0 || W < 0 || Cout < 1) return 1;
+    if (kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0) return 1;
+    if (kh > H + 2 * (int64_t)ph || kw > W + 2 * (int64_t)pw) return 1;
+    const int64_t Ho = (H + 2 * (int64_t)ph - kh) / sh + 1;
+    const int64_t Wo = (W + 2 * (int64_t)pw - kw) / sw + 1;
+    if (!out || (N > 0 && (!other || !gy))) return 1;
+    const int64_t n_out = which == 0 ? N * Cin * H * W : Cout * Cin * kh * kw;
+    for (int64_t e = 0; e < n_out; ++e) {
+        out[e] = 0.0;
+        if (abs_sum) abs_sum[e] = 0.0;
+    }
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t co = 0; co < Cout; ++co)
+            for (int64_t ho = 0; ho < Ho; ++ho)
+                for (int64_t wo = 0; wo < Wo; ++wo) {
+                    const double g = (double)gy[((n * Cout + co) * Ho + ho) * Wo + wo];
+                    for (int64_t ci = 0; ci < Cin; ++ci)
+                        for (int32_t a = 0; a < kh; ++a)
+                            for (int32_t b = 0; b < kw; ++b) {
+                                const int64_t h = ho * sh - ph + a, c = wo * sw - pw + b;
+                                if (h < 0 || h >= H || c < 0 || c >= W) continue;
+                                const int64_t xi = ((n * Cin + ci) * H + h) * W + c;
+                                const int64_t wi = ((co * Cin + ci) * kh + a) * kw + b;
+                                const double term = (double)other[which == 0 ? wi : xi] * g;
+                                const int64_t at = which == 0 ? xi : wi;
+                                out[at] += term;
+                                if (abs_sum) abs_sum[at] += fabs(term);
+                            }
+                }
+    return 0;
+}
+
+int sws_ref_conv2d_grad_input(const float *gy, const float *wgt, double *gx, double *abs_sum,
+                              int64_t N, int64_t Cin, int64_t H, int64_t W, int64_t Cout,
+                              int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw)
+{
+    return conv2d_adjoint(0, wgt, gy, gx, abs_sum, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw);
+}
+
+int sws_ref_conv2d_grad_weight(const float *x, const float *gy, double *gw, double *abs_sum,
+                               int64_t N, int64_t Cin, int64_t H, int64_t W, int64_t Cout,
+                               int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw)
+{
+    return conv2d_adjoint(1, x, gy, gw, abs_sum, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw);
 }

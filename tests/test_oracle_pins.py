@@ -864,3 +864,52 @@ def test_padded_shrinking_window_hand_written_and_closed_forms():
         assert np.array_equal(m0, m4)
     with pytest.raises(ValueError):
         oracle.slide1d_padded(oracle.OP_ADD, z, 3, 3, 0, oracle.PAD_SHRINK)
+
+
+# ----------------------------------------------------------------------------- P15
+# The adjoints of the 2-D sliding dot product (scatter form).
+@pytest.mark.parametrize("case", [(2, 3, 9, 8, 4, 3, 3, 1, 1, 1, 1), (1, 2, 10, 7, 3, 2, 4, 2, 1, 0, 2), (2, 4, 6, 6, 2, 1, 1, 1, 1, 0, 0),
+                                  (1, 3, 11, 9, 2, 5, 3, 2, 3, 2, 1)])
+def test_conv2d_adjoints_inner_product_identities_and_central_differences(case):
+    n, cin, h, wd, cout, kh, kw, sh, sw, ph, pw = case
+    r = _rng(210 + kh + kw)
+    x = r.integers(-3, 4, (n, cin, h, wd)).astype(np.float32)
+    w = r.integers(-3, 4, (cout, cin, kh, kw)).astype(np.float32)
+    y, _ = oracle.conv2d(x, w, sh, sw, ph, pw)
+    g = r.integers(-3, 4, y.shape).astype(np.float32)
+    gx, _ = oracle.conv2d_grad_input(g, w, h, wd, sh, sw, ph, pw)
+    gw, _ = oracle.conv2d_grad_weight(x, g, kh, kw, sh, sw, ph, pw)
+    loss = float((y * g).sum())
+    assert loss == float((x.astype(np.float64) * gx).sum()) == float((w.astype(np.float64) * gw).sum())
+    f = lambda xx, ww: float((oracle.conv2d(xx, ww, sh, sw, ph, pw)[0] * g).sum())
+    for idx in list(np.ndindex(x.shape))[::7]:
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += 1
+        xm[idx] -= 1
+        assert (f(xp, w) - f(xm, w)) / 2 == gx[idx]
+    for idx in list(np.ndindex(w.shape))[::3]:
+        wp, wm = w.copy(), w.copy()
+        wp[idx] += 1
+        wm[idx] -= 1
+        assert (f(x, wp) - f(x, wm)) / 2 == gw[idx]
+
+
+def test_conv2d_adjoints_on_one_row_planes_are_the_1d_adjoints_and_a_hand_case():
+    r = _rng(220)
+    x = r.standard_normal((2, 3, 1, 23), dtype=np.float32)
+    w = r.standard_normal((4, 3, 1, 5), dtype=np.float32)
+    g = r.standard_normal((2, 4, 1, 23), dtype=np.float32)
+    gx2, _ = oracle.conv2d_grad_input(g, w, 1, 23, 1, 1, 0, 2)
+    gw2, _ = oracle.conv2d_grad_weight(x, g, 1, 5, 1, 1, 0, 2)
+    gx1, _ = oracle.conv1d_grad_input(g[:, :, 0], w[:, :, 0], 23, 1, 2, 1, 1)
+    gw1, _ = oracle.conv1d_grad_weight(x[:, :, 0], g[:, :, 0], 5, 1, 2, 1, 1)
+    assert np.abs(gx2[:, :, 0] - gx1).max() < 1e-12 and np.abs(gw2[:, :, 0] - gw1).max() < 1e-12
+    # one gradient at output (1, 0) of a 3 x 3 plane, 2 x 2 taps, no padding: it reads x[1:3, 0:2]
+    xh = np.arange(1, 10, dtype=np.float32).reshape(1, 1, 3, 3)
+    wh = np.array([[[[10, 20], [30, 40]]]], np.float32)
+    gh = np.zeros((1, 1, 2, 2), np.float32)
+    gh[0, 0, 1, 0] = 2
+    gx, _ = oracle.conv2d_grad_input(gh, wh, 3, 3)
+    assert gx[0, 0].tolist() == [[0, 0, 0], [20, 40, 0], [60, 80, 0]]
+    gw, _ = oracle.conv2d_grad_weight(xh, gh, 2, 2)
+    assert gw[0, 0].tolist() == [[8, 10], [14, 16]]
