@@ -298,6 +298,17 @@ def sweeps_table(torch, B, workloads, iters=20):
         ms = time_launches(torch, fn, iters)
         out["adjoints"][name] = {"us": round(ms * 1e3, 2), "TFLOPs": round(fl / ms / 1e9, 2),
                                  "frac_fp32_mfma_peak": round(fl / ms / 1e9 / 157.3, 4)}
+    x4, w4 = workloads.make(4)
+    x4, w4 = g(x4), g(w4)
+    gy4 = torch.empty(32, 64, 56, 56, device="cuda").normal_()
+    gx4, gw4 = torch.empty_like(x4), torch.empty_like(w4)
+    fl = 7398752256.0
+    for name, fn in (("cfg4_conv2d_grad_input", lambda: B.sws_conv2d_grad_input(gy4, w4, 56, 56, 1, 1, 1, 1, gx=gx4)),
+                     ("cfg4_conv2d_grad_weight", lambda: B.sws_conv2d_grad_weight(x4, gy4, 3, 3, 1, 1, 1, 1, gw=gw4))):
+        ms = time_launches(torch, fn, iters)
+        out["adjoints"][name] = {"us": round(ms * 1e3, 2), "TFLOPs": round(fl / ms / 1e9, 2),
+                                 "frac_fp32_mfma_peak": round(fl / ms / 1e9 / 157.3, 4)}
+    del x4, gy4, gx4
     xr = torch.empty(32, 256, 3136, device="cuda").normal_()
     gr = torch.empty(32, 256, 3136, device="cuda").normal_()
     wr = torch.empty(256, 256, 3, device="cuda").normal_()
@@ -340,6 +351,16 @@ def run_only(torch, B, workloads, name, steps):
         else:
             gw = torch.empty_like(w2)
             fn = lambda: B.sws_conv1d_grad_weight(x2, gy, 3, gw=gw)
+    elif name in ("grad_input_cfg4", "grad_weight_cfg4"):
+        x4, w4 = workloads.make(4)
+        x4, w4 = g(x4), g(w4)
+        gy = torch.empty(32, 64, 56, 56, device="cuda").normal_()
+        if name.startswith("grad_input"):
+            gx = torch.empty_like(x4)
+            fn = lambda: B.sws_conv2d_grad_input(gy, w4, 56, 56, 1, 1, 1, 1, gx=gx)
+        else:
+            gw = torch.empty_like(w4)
+            fn = lambda: B.sws_conv2d_grad_weight(x4, gy, 3, 3, 1, 1, 1, 1, gw=gw)
     elif name.startswith("slide16_"):                     # slide16_<bf16|f16>_<add|max>_w<w>
         _, dn, opn, wn = name.split("_")
         w = int(wn[1:])

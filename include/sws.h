@@ -202,6 +202,24 @@ sws_status sws_conv2d(const float *x, const float *wgt, float *y, int64_t N, int
                       int64_t H, int64_t W, int64_t Cout, int32_t kh, int32_t kw,
                       int32_t sh, int32_t sw, int32_t ph, int32_t pw, void *stream);
 
+/* The two adjoints of sws_conv2d, defined like those of sws_conv1d (loss = sum(gy * y)):
+ *   gx[n,ci,h,c]     = sum over (co, a, b) with h + ph - a = ho*sh, c + pw - b = wo*sw inside the
+ *                      output:  wgt[co,ci,a,b] * gy[n,co,ho,wo]
+ *   gw[co,ci,a,b]    = sum over (n, ho, wo) whose tap (a, b) lies inside the plane:
+ *                      gy[n,co,ho,wo] * x[n,ci, ho*sh - ph + a, wo*sw - pw + b]
+ * Sizes are those of the forward call.  gx and gw are overwritten; gw is summed with atomic adds
+ * whose order is not fixed.
+ *   gy : device [N,Cout,Ho,Wo]   wgt, gw : device [Cout,Cin,kh,kw]   x, gx : device [N,Cin,H,W]
+ * Errors: as sws_conv2d. */
+sws_status sws_conv2d_grad_input(const float *gy, const float *wgt, float *gx, int64_t N,
+                                 int64_t Cin, int64_t H, int64_t W, int64_t Cout, int32_t kh,
+                                 int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
+                                 void *stream);
+sws_status sws_conv2d_grad_weight(const float *x, const float *gy, float *gw, int64_t N,
+                                  int64_t Cin, int64_t H, int64_t W, int64_t Cout, int32_t kh,
+                                  int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
+                                  void *stream);
+
 /* Plain device-to-device copy of n floats with the same 128-bit access pattern the
  * sliding kernels use.  Not part of the method: it measures the HBM ceiling a
  * one-read-one-write kernel can reach on this device, and calibrates byte counters. */

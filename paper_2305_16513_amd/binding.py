@@ -19,7 +19,7 @@ _lib = None
 
 _i64, _i32, _f32, _vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
 
-EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_pool2d_ex", "sws_conv1d", "sws_conv1d_grad_input", "sws_conv1d_grad_weight", "sws_conv2d", "sws_copy", "sws_out_len",
+EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_pool2d_ex", "sws_conv1d", "sws_conv1d_grad_input", "sws_conv1d_grad_weight", "sws_conv2d", "sws_conv2d_grad_input", "sws_conv2d_grad_weight", "sws_copy", "sws_out_len",
            "sws_status_string", "sws_set_option", "sws_version")
 
 
@@ -59,6 +59,9 @@ def lib():
         L.sws_conv2d.restype = ctypes.c_int
         L.sws_conv2d.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64,
                                  _i32, _i32, _i32, _i32, _i32, _i32, _vp]
+        for f in (L.sws_conv2d_grad_input, L.sws_conv2d_grad_weight):
+            f.restype = ctypes.c_int
+            f.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _i32, _vp]
         L.sws_copy.restype = ctypes.c_int
         L.sws_copy.argtypes = [_vp, _vp, _i64, _vp]
         L.sws_out_len.restype = _i64
@@ -284,6 +287,34 @@ def sws_conv2d(x, wgt, sh=1, sw=1, ph=0, pw=0, y=None, stream=None):
     _check(lib().sws_conv2d(x.data_ptr(), wgt.data_ptr(), y.data_ptr(), n, cin, h, wd, cout, kh, kw,
                             sh, sw, ph, pw, _stream(stream)), "sws_conv2d")
     return y
+
+
+def sws_conv2d_grad_input(gy, wgt, h, wd, sh=1, sw=1, ph=0, pw=0, gx=None, stream=None):
+    """gy [N, Cout, Ho, Wo], wgt [Cout, Cin, kh, kw], (h, wd) = the forward input's plane -> gx [N, Cin, H, W]."""
+    _dev(gy, "gy")
+    _dev(wgt, "wgt")
+    n, cout, ho, wo = gy.shape
+    cout2, cin, kh, kw = wgt.shape
+    if cout2 != cout or ho != sws_out_len(h, kh, sh, ph) or wo != sws_out_len(wd, kw, sw, pw):
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_conv2d_grad_input")
+    gx = _out(gx, (n, cin, h, wd), gy, "gx")
+    _check(lib().sws_conv2d_grad_input(gy.data_ptr(), wgt.data_ptr(), gx.data_ptr(), n, cin, h, wd, cout, kh, kw,
+                                       sh, sw, ph, pw, _stream(stream)), "sws_conv2d_grad_input")
+    return gx
+
+
+def sws_conv2d_grad_weight(x, gy, kh, kw, sh=1, sw=1, ph=0, pw=0, gw=None, stream=None):
+    """x [N, Cin, H, W], gy [N, Cout, Ho, Wo] -> gw [Cout, Cin, kh, kw]."""
+    _dev(x, "x")
+    _dev(gy, "gy")
+    n, cin, h, wd = x.shape
+    n2, cout, ho, wo = gy.shape
+    if n2 != n or ho != sws_out_len(h, kh, sh, ph) or wo != sws_out_len(wd, kw, sw, pw):
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_conv2d_grad_weight")
+    gw = _out(gw, (cout, cin, kh, kw), x, "gw")
+    _check(lib().sws_conv2d_grad_weight(x.data_ptr(), gy.data_ptr(), gw.data_ptr(), n, cin, h, wd, cout, kh, kw,
+                                        sh, sw, ph, pw, _stream(stream)), "sws_conv2d_grad_weight")
+    return gw
 
 
 def sws_copy(src, dst=None, stream=None):

@@ -221,12 +221,21 @@ __global__ __launch_bounds__(kThreads) void conv1d_thin_grad_weight_kernel(
 constexpr int kPw = 64;                              // positions per wavefront slab
 constexpr int kGPitch = kPw + 2;
 
+// The same kernel serves the 2-D convolution: its contraction runs over (image, output row,
+// position in the row), and a tap group is one kernel row a (or a part of it): the x row that
+// output row ho meets is ho*sh - ph + a, or none (zeros) outside the plane.  1-D: H = Ho = kh = 1.
+struct GwGeom {
+    int Cin, Cout, L, Lo, k, pad, dilation;          // row lengths of x and gy, taps per kernel row, left padding
+    int H, Ho, kh, sh, ph;                           // rows of x and gy per image, kernel rows, row stride, top padding
+    int64_t x_cs, gy_cs;                             // channel strides (H*L, Ho*Lo)
+};
+
 template <int KT, int XC>
 __global__ __launch_bounds__(kThreads) void conv1d_dense_grad_weight_kernel(
-    const float *__restrict__ x, const float *__restrict__ gy, float *__restrict__ gw, int Cin, int L, int Cout,
-    int Lo, int k, int pad, int dilation, int XPITCH, int slabs_per_row, int64_t total_slabs, int slabs,
-    int co_blocks, int ci_blocks, int tap_groups)
+    const float *__restrict__ x, const float *__restrict__ gy, float *__restrict__ gw, GwGeom gm, int XPITCH,
+    int slabs_per_row, int64_t total_slabs, int slabs, int co_blocks, int ci_blocks, int tap_groups)
 {
+    const int Cin = gm.Cin, Cout = gm.Cout, L = gm.L, Lo = gm.Lo, k = gm.k, pad = gm.pad, dilation = gm.dilation;
     extern __shared__ __attribute__((aligned(16))) float lds_dyn[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -236,12 +245,14 @@ __global__ __launch_bounds__(kThreads) void conv1d_dense_grad_weight_kernel(
     float *Xl = Gl + 32 * kGPitch;                   // [32][XPITCH]
 
     int64_t u = blockIdx.x;
-    const int tg = (int)(u % tap_groups); u /= tap_groups;
+    const int tg_all = (int)(u % tap_groups); u /= tap_groups;
     const int cib = (int)(u % ci_blocks); u /= ci_blocks;
     const int cob = (int)(u % co_blocks); u /= co_blocks;
     const int64_t slab0 = u * slabs;
     int64_t slab1 = slab0 + slabs;
     if (slab1 > total_slabs) slab1 = total_slabs;
+    const int groups_per_krow = tap_groups / gm.kh;  // tap groups of one kernel row
+    const int ka = tg_all / groups_per_krow, tg = tg_all - ka * groups_per_krow;     // my kernel row, my group in it
     const int co0 = cob * 32, ci0 = cib * 32, t0 = tg * KT;
     const int nt = (k - t0 < KT) ? k - t0 : KT;      // live taps of this group
     const int xw = kPw + (KT - 1) * dilation;        // staged x positions per slab
@@ -269,17 +280,23 @@ __global__ __launch_bounds__(kThreads) void conv1d_dense_grad_weight_kernel(
         return r;
     };
     auto prefetch = [&](int64_t slab) {
-        const int64_t b = slab / slabs_per_row;
-        const int i0 = (int)(slab - b * slabs_per_row) * kPw;
+        const int64_t rho = slab / slabs_per_row;    // (image, output row)
+        const int i0 = (int)(slab - rho * slabs_per_row) * kPw;
         const int j0 = i0 + t0 * dilation - pad;
+        const int64_t b = rho / gm.Ho;
+        const int ho = (int)(rho - b * gm.Ho);
+        const int h = ho * gm.sh - gm.ph + ka;       // the x row this output row meets under kernel row ka
+        const bool h_ok = h >= 0 && h < gm.H;
+        const float *gyb = gy + b * Cout * gm.gy_cs + (int64_t)ho * Lo;
+        const float *xb_ = x + b * Cin * gm.x_cs + (int64_t)(h_ok ? h : 0) * L;
 #pragma unroll
         for (int p = 0; p < GV; ++p) {
             const int row = 4 * p + srow;
             const int co = co0 + row, ci = ci0 + row;
-            greg[p] = load4(gy + (b * Cout + (co < Cout ? co : 0)) * (int64_t)Lo, i0 + scol, Lo, co < Cout);
+            greg[p] = load4(gyb + (co < Cout ? co : 0) * gm.gy_cs, i0 + scol, Lo, co < Cout);
 #pragma unroll
             for (int c = 0; c < XCMAX; ++c) {
-                xreg[c][p] = load4(x + (b * Cin + (ci < Cin ? ci : 0)) * (int64_t)L, j0 + 64 * c + scol, L, ci < Cin);
+                xreg[c][p] = load4(xb_ + (ci < Cin ? ci : 0) * gm.x_cs, j0 + 64 * c + scol, L, h_ok && ci < Cin);
             }
         }
     };
@@ -337,7 +354,7 @@ __global__ __launch_bounds__(kThreads) void conv1d_dense_grad_weight_kernel(
 #pragma unroll
         for (int wv = 0; wv < kWavesPerWg; ++wv) v += lds_dyn[wv * (32 * RP) + row * RP + rest];
         if (co0 + row < Cout && ci0 + ci < Cin && t < nt)
-            atomicAdd(gw + ((int64_t)(co0 + row) * Cin + ci0 + ci) * k + t0 + t, v);
+            atomicAdd(gw + (((int64_t)(co0 + row) * Cin + ci0 + ci) * gm.kh + ka) * k + t0 + t, v);
     }
 }
 
@@ -358,23 +375,28 @@ hipError_t launch_thin_gw(const float *x, const float *gy, float *gw, int B, int
 }
 
 template <int KT>
-hipError_t launch_dense_gw(const float *x, const float *gy, float *gw, int64_t B, int Cin, int L, int Cout, int Lo,
-                           int k, int pad, int dilation, hipStream_t s, bool *taken)
+hipError_t launch_dense_gw(const float *x, const float *gy, float *gw, int64_t B, const GwGeom &gm, hipStream_t s,
+                           bool *taken)
 {
-    const int xw = kPw + (KT - 1) * dilation;
+    const int xw = kPw + (KT - 1) * gm.dilation;
     const int XPITCH = (xw + 61) / 64 * 64 + 2;      // >= xw, = 2 mod 64
     const size_t stage = (size_t)kWavesPerWg * (32 * kGPitch + 32 * XPITCH) * sizeof(float);
     const size_t red = (size_t)kWavesPerWg * 32 * (32 * KT + 1) * sizeof(float);
     const size_t lds = stage > red ? stage : red;
     *taken = lds <= 128 * 1024 && xw <= 256;        // above 64 KB the kernel's LDS limit is raised below
     if (!*taken) return hipSuccess;
-    const int slabs_per_row = (Lo + kPw - 1) / kPw;
-    const int64_t total_slabs = B * slabs_per_row;
-    const int co_blocks = (Cout + 31) / 32, ci_blocks = (Cin + 31) / 32, tap_groups = (k + KT - 1) / KT;
+    const int slabs_per_row = (gm.Lo + kPw - 1) / kPw;
+    const int64_t total_slabs = B * gm.Ho * slabs_per_row;
+    const int co_blocks = (gm.Cout + 31) / 32, ci_blocks = (gm.Cin + 31) / 32;
+    const int tap_groups = gm.kh * ((gm.k + KT - 1) / KT);
     const int64_t blocks = (int64_t)co_blocks * ci_blocks * tap_groups;
-    // slabs per workgroup: at least one per wavefront, and about 512 workgroups in all (measured on
-    // x[16,64,4096], 64 -> 64 channels, k = 3: 47 us with 1024 workgroups, 41 with 512, 70 with 128)
-    int64_t slabs = (total_slabs * blocks + 511) / 512;
+    // Split of the contraction over workgroups: about 128 per block of gw (each ends with atomic
+    // adds to the same cache lines, which serialise), more when there are so few blocks that 128
+    // would leave the device idle; at least one slab per wavefront.  Measured, slabs per workgroup
+    // 8 / 12 / 16 / 32 / 64: x[16,64,4096], 64 -> 64, k = 3 (4 blocks, 1024 slabs): 39 / 44 / 44 / 70 /
+    // 124 us; [32,64,56,56], 3 x 3 (12 blocks, 1792 slabs): 199 / 176 / 180 / 190 / 204 us.
+    int64_t nsplit = 512 / blocks > 128 ? 512 / blocks : 128;
+    int64_t slabs = (total_slabs + nsplit - 1) / nsplit;
     if (slabs < kWavesPerWg) slabs = kWavesPerWg;
     if (g_opt.slide_group > 0) slabs = g_opt.slide_group;           // A/B: slabs per workgroup
     const int64_t grid = blocks * ((total_slabs + slabs - 1) / slabs);
@@ -387,8 +409,8 @@ hipError_t launch_dense_gw(const float *x, const float *gy, float *gw, int64_t B
             if (ea != hipSuccess) return ea;                                                                      \
         }                                                                                                         \
         hipLaunchKernelGGL((conv1d_dense_grad_weight_kernel<KT, XC>), dim3((unsigned)grid), dim3(kThreads), lds, s, x, \
-                           gy, gw, Cin, L, Cout, Lo, k, pad, dilation, XPITCH, slabs_per_row, total_slabs, (int)slabs, \
-                           co_blocks, ci_blocks, tap_groups);                                                     \
+                           gy, gw, gm, XPITCH, slabs_per_row, total_slabs, (int)slabs, co_blocks, ci_blocks,      \
+                           tap_groups);                                                                           \
         break
     switch ((xw + 63) / 64) {
         SWS_DGW(1); SWS_DGW(2); SWS_DGW(3); SWS_DGW(4);
@@ -398,7 +420,118 @@ hipError_t launch_dense_gw(const float *x, const float *gy, float *gw, int64_t B
     return hipGetLastError();
 }
 
+// taps per workgroup: all of a kernel row up to 4, else groups of 4 (16 accumulator registers per tap)
+hipError_t launch_dense_gw_taps(const float *x, const float *gy, float *gw, int64_t B, const GwGeom &gm, hipStream_t s,
+                                bool *taken)
+{
+    if (gm.k == 1) return launch_dense_gw<1>(x, gy, gw, B, gm, s, taken);
+    if (gm.k == 2) return launch_dense_gw<2>(x, gy, gw, B, gm, s, taken);
+    if (gm.k == 3) return launch_dense_gw<3>(x, gy, gw, B, gm, s, taken);
+    return launch_dense_gw<4>(x, gy, gw, B, gm, s, taken);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Direct evaluation of the 2-D adjoints.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void conv2d_grad_input_naive_kernel(
+    const float *__restrict__ gy, const float *__restrict__ wgt, float *__restrict__ gx, int64_t N, int Cin, int H,
+    int W, int Cout, int Ho, int Wo, int kh, int kw, int sh, int sw, int ph, int pw)
+{
+    const int64_t total = N * (int64_t)Cin * H * W;
+    for (int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x; o < total; o += (int64_t)gridDim.x * kThreads) {
+        const int c = (int)(o % W);
+        const int h = (int)((o / W) % H);
+        const int ci = (int)((o / ((int64_t)W * H)) % Cin);
+        const int64_t n = o / ((int64_t)W * H * Cin);
+        float acc = 0.0f;
+        for (int a = 0; a < kh; ++a) {
+            const int nh = h + ph - a;
+            if (nh < 0 || nh % sh || nh / sh >= Ho) continue;
+            for (int b = 0; b < kw; ++b) {
+                const int nw = c + pw - b;
+                if (nw < 0 || nw % sw || nw / sw >= Wo) continue;
+                for (int co = 0; co < Cout; ++co)
+                    acc += wgt[(((int64_t)co * Cin + ci) * kh + a) * kw + b] *
+                           gy[((n * Cout + co) * (int64_t)Ho + nh / sh) * Wo + nw / sw];
+            }
+        }
+        gx[o] = acc;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void conv2d_grad_weight_naive_kernel(
+    const float *__restrict__ x, const float *__restrict__ gy, float *__restrict__ gw, int64_t N, int Cin, int H, int W,
+    int Cout, int Ho, int Wo, int kh, int kw, int sh, int sw, int ph, int pw)
+{
+    __shared__ float part[kThreads];
+    const int64_t e = blockIdx.x;                    // ((co * Cin + ci) * kh + a) * kw + b
+    const int b = (int)(e % kw);
+    const int a = (int)((e / kw) % kh);
+    const int ci = (int)((e / ((int64_t)kw * kh)) % Cin);
+    const int co = (int)(e / ((int64_t)kw * kh * Cin));
+    float acc = 0.0f;
+    const int64_t cnt = N * (int64_t)Ho * Wo;
+    for (int64_t o = threadIdx.x; o < cnt; o += kThreads) {
+        const int wo = (int)(o % Wo);
+        const int ho = (int)((o / Wo) % Ho);
+        const int64_t n = o / ((int64_t)Wo * Ho);
+        const int h = ho * sh - ph + a, c = wo * sw - pw + b;
+        if (h >= 0 && h < H && c >= 0 && c < W)
+            acc += gy[((n * Cout + co) * (int64_t)Ho + ho) * Wo + wo] * x[((n * Cin + ci) * (int64_t)H + h) * W + c];
+    }
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int hh = kThreads / 2; hh > 0; hh >>= 1) {
+        if ((int)threadIdx.x < hh) part[threadIdx.x] += part[threadIdx.x + hh];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) gw[e] = part[0];
+}
+
 }  // namespace
+
+// Adjoints of sws_conv2d.  With respect to the input at stride 1: the matrix-core kernel on the
+// output gradients, weights read through the adjoint view (both tap axes reversed = the flattened
+// tap index reversed), padding (kh-1-ph, kw-1-pw).  With respect to the weights at horizontal
+// stride 1: the dense kernel above, one kernel row per tap group.
+hipError_t launch_conv2d_grad_input(const float *gy, const float *wgt, float *gx, int64_t N, int64_t Cin, int64_t H,
+                                    int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh,
+                                    int32_t sw, int32_t ph, int32_t pw, hipStream_t s)
+{
+    if (sh == 1 && sw == 1 && ph <= kh - 1 && pw <= kw - 1 && g_opt.conv2d_variant != 1) {
+        bool taken = false;
+        const hipError_t e = launch_conv2d_mfma(gy, wgt, gx, N, Cout, Ho, Wo, Cin, H, W, kh, kw, 1, 1, kh - 1 - ph,
+                                                kw - 1 - pw, 1, 1, s, &taken, 1);
+        if (taken || e != hipSuccess) return e;
+    }
+    int64_t grid = (N * Cin * H * W + kThreads - 1) / kThreads;
+    if (grid > 1048576) grid = 1048576;
+    hipLaunchKernelGGL(conv2d_grad_input_naive_kernel, dim3((unsigned)grid), dim3(kThreads), 0, s, gy, wgt, gx, N,
+                       (int)Cin, (int)H, (int)W, (int)Cout, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw);
+    return hipGetLastError();
+}
+
+hipError_t launch_conv2d_grad_weight(const float *x, const float *gy, float *gw, int64_t N, int64_t Cin, int64_t H,
+                                     int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh,
+                                     int32_t sw, int32_t ph, int32_t pw, hipStream_t s)
+{
+    const int64_t n_gw = Cout * Cin * kh * kw;
+    if (n_gw > 2147483647LL) return hipErrorInvalidValue;
+    if (N > 0 && sw == 1 && Cin >= 2 && g_opt.conv2d_variant != 1 && H * W <= 2147483647LL && Ho * Wo <= 2147483647LL) {
+        int64_t fg = (n_gw + kThreads - 1) / kThreads;
+        if (fg > 4096) fg = 4096;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)fg), dim3(kThreads), 0, s, gw, n_gw);
+        GwGeom gm;
+        gm.Cin = (int)Cin; gm.Cout = (int)Cout; gm.L = (int)W; gm.Lo = (int)Wo; gm.k = kw; gm.pad = pw; gm.dilation = 1;
+        gm.H = (int)H; gm.Ho = (int)Ho; gm.kh = kh; gm.sh = sh; gm.ph = ph; gm.x_cs = H * W; gm.gy_cs = Ho * Wo;
+        bool taken = false;
+        const hipError_t e = launch_dense_gw_taps(x, gy, gw, N, gm, s, &taken);
+        if (taken || e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(conv2d_grad_weight_naive_kernel, dim3((unsigned)n_gw), dim3(kThreads), 0, s, x, gy, gw, N,
+                       (int)Cin, (int)H, (int)W, (int)Cout, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw);
+    return hipGetLastError();
+}
 
 hipError_t launch_conv1d_grad_input(const float *gy, const float *wgt, float *gx, int64_t B, int64_t Cin, int64_t L,
                                     int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad,
@@ -446,13 +579,11 @@ hipError_t launch_conv1d_grad_weight(const float *x, const float *gy, float *gw,
 #undef SWS_TGW
     }
     if (dense_ok) {
+        GwGeom gm;
+        gm.Cin = (int)Cin; gm.Cout = (int)Cout; gm.L = (int)L; gm.Lo = (int)Lo; gm.k = k; gm.pad = pad; gm.dilation = dilation;
+        gm.H = 1; gm.Ho = 1; gm.kh = 1; gm.sh = 1; gm.ph = 0; gm.x_cs = L; gm.gy_cs = Lo;
         bool taken = false;
-        hipError_t e;
-        // taps per workgroup: all of them up to 4, else groups of 4 (16 accumulator registers per tap)
-        if (k == 1) e = launch_dense_gw<1>(x, gy, gw, B, (int)Cin, (int)L, (int)Cout, (int)Lo, k, pad, dilation, s, &taken);
-        else if (k == 2) e = launch_dense_gw<2>(x, gy, gw, B, (int)Cin, (int)L, (int)Cout, (int)Lo, k, pad, dilation, s, &taken);
-        else if (k == 3) e = launch_dense_gw<3>(x, gy, gw, B, (int)Cin, (int)L, (int)Cout, (int)Lo, k, pad, dilation, s, &taken);
-        else e = launch_dense_gw<4>(x, gy, gw, B, (int)Cin, (int)L, (int)Cout, (int)Lo, k, pad, dilation, s, &taken);
+        const hipError_t e = launch_dense_gw_taps(x, gy, gw, B, gm, s, &taken);
         if (taken || e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(conv1d_grad_weight_naive_kernel, dim3((unsigned)n_gw), dim3(kThreads), 0, s, x, gy, gw, B,

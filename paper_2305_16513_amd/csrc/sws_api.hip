@@ -235,6 +235,52 @@ sws_status sws_conv1d_grad_weight(const float *x, const float *gy, float *gw, in
                                                    (hipStream_t)stream));
 }
 
+namespace {
+
+sws_status check_conv2d(int64_t N, int64_t Cin, int64_t H, int64_t W, int64_t Cout, int32_t kh, int32_t kw, int32_t sh,
+                        int32_t sw, int32_t ph, int32_t pw, int64_t *Ho, int64_t *Wo)
+{
+    if (N < 0 || Cin < 1 || H < 0 || W < 0 || Cout < 1) return SWS_ERR_INVALID_ARG;
+    if (kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0) return SWS_ERR_INVALID_ARG;
+    if (H > kMaxDim || W > kMaxDim || Cin > kMaxDim || Cout > kMaxDim) return SWS_ERR_INVALID_ARG;
+    *Ho = sws_out_len(H, kh, sh, ph, 1);
+    *Wo = sws_out_len(W, kw, sw, pw, 1);
+    if (*Ho < 1 || *Wo < 1) return SWS_ERR_INVALID_ARG;
+    int64_t t, n_in, n_out, n_w;
+    if (!mul3(N, Cin, H, &t) || !mul3(t, W, 1, &n_in)) return SWS_ERR_INVALID_ARG;
+    if (!mul3(N, Cout, *Ho, &t) || !mul3(t, *Wo, 1, &n_out)) return SWS_ERR_INVALID_ARG;
+    if (!mul3(Cout, Cin, (int64_t)kh * kw, &n_w)) return SWS_ERR_INVALID_ARG;
+    if (H * W > kMaxDim || *Ho * *Wo > kMaxDim || n_w > kMaxDim) return SWS_ERR_UNSUPPORTED;
+    return SWS_OK;
+}
+
+}  // namespace
+
+sws_status sws_conv2d_grad_input(const float *gy, const float *wgt, float *gx, int64_t N, int64_t Cin, int64_t H,
+                                 int64_t W, int64_t Cout, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph,
+                                 int32_t pw, void *stream)
+{
+    int64_t Ho, Wo;
+    const sws_status st = check_conv2d(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, &Ho, &Wo);
+    if (st != SWS_OK) return st;
+    if (N == 0) return SWS_OK;
+    if (!gy || !wgt || !gx) return SWS_ERR_INVALID_ARG;
+    return from_hip(sws::launch_conv2d_grad_input(gy, wgt, gx, N, Cin, H, W, Cout, Ho, Wo, kh, kw, sh, sw, ph, pw,
+                                                  (hipStream_t)stream));
+}
+
+sws_status sws_conv2d_grad_weight(const float *x, const float *gy, float *gw, int64_t N, int64_t Cin, int64_t H,
+                                  int64_t W, int64_t Cout, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph,
+                                  int32_t pw, void *stream)
+{
+    int64_t Ho, Wo;
+    const sws_status st = check_conv2d(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, &Ho, &Wo);
+    if (st != SWS_OK) return st;
+    if (!gw || (N > 0 && (!x || !gy))) return SWS_ERR_INVALID_ARG;      // with no images gw is all zeros
+    return from_hip(sws::launch_conv2d_grad_weight(x, gy, gw, N, Cin, H, W, Cout, Ho, Wo, kh, kw, sh, sw, ph, pw,
+                                                   (hipStream_t)stream));
+}
+
 sws_status sws_conv2d(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
                       int64_t W, int64_t Cout, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph,
                       int32_t pw, void *stream)

@@ -92,6 +92,12 @@ hipError_t launch_conv1d_grad_input(const float *gy, const float *wgt, float *gx
 hipError_t launch_conv1d_grad_weight(const float *x, const float *gy, float *gw, int64_t B, int64_t Cin, int64_t L,
                                      int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad,
                                      int32_t dilation, int32_t groups, hipStream_t s);
+hipError_t launch_conv2d_grad_input(const float *gy, const float *wgt, float *gx, int64_t N, int64_t Cin, int64_t H,
+                                    int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh,
+                                    int32_t sw, int32_t ph, int32_t pw, hipStream_t s);
+hipError_t launch_conv2d_grad_weight(const float *x, const float *gy, float *gw, int64_t N, int64_t Cin, int64_t H,
+                                     int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh,
+                                     int32_t sw, int32_t ph, int32_t pw, hipStream_t s);
 hipError_t launch_conv2d(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
                          int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw,
                          int32_t sh, int32_t sw, int32_t ph, int32_t pw, hipStream_t s);

@@ -141,3 +141,52 @@ def test_argument_checks(B):
     assert L.sws_conv1d_grad_weight(None, None, gw.data_ptr(), 0, 4, 100, 4, 3, 1, 0, 1, 4, None) == B.SWS_OK
     torch.cuda.synchronize()
     assert float(gw.abs().sum()) == 0.0
+
+
+# ------------------------------------------------------------------------------ 2-D
+# N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw
+CASES_2D = [(2, 64, 20, 20, 64, 3, 3, 1, 1, 1, 1), (2, 16, 13, 17, 24, 3, 3, 1, 1, 0, 0), (1, 8, 30, 9, 40, 5, 5, 1, 1, 2, 2),
+            (2, 32, 14, 14, 32, 1, 1, 1, 1, 0, 0), (1, 24, 12, 70, 8, 2, 4, 1, 1, 1, 3), (2, 8, 15, 15, 8, 3, 3, 2, 2, 1, 1),
+            (1, 6, 11, 12, 10, 3, 3, 1, 1, 1, 1), (2, 16, 16, 16, 16, 3, 3, 2, 1, 1, 1), (1, 40, 9, 140, 72, 3, 7, 1, 1, 1, 3)]
+
+
+def _data2d(case, seed, integer=False):
+    n, cin, h, wd, cout, kh, kw, sh, sw, ph, pw = case
+    ho, wo = (h + 2 * ph - kh) // sh + 1, (wd + 2 * pw - kw) // sw + 1
+    if integer:
+        return (workloads.integer_valued((n, cin, h, wd), -3, 3, seed), workloads.integer_valued((cout, cin, kh, kw), -3, 3, seed + 1),
+                workloads.integer_valued((n, cout, ho, wo), -3, 3, seed + 2))
+    r = np.random.Generator(np.random.PCG64(seed))
+    return (r.standard_normal((n, cin, h, wd), dtype=np.float32),
+            (r.standard_normal((cout, cin, kh, kw), dtype=np.float32) * np.float32(0.2)).astype(np.float32),
+            r.standard_normal((n, cout, ho, wo), dtype=np.float32))
+
+
+@pytest.mark.parametrize("integer", [False, True])
+@pytest.mark.parametrize("case", CASES_2D)
+def test_conv2d_adjoints(B, case, integer):
+    n, cin, h, wd, cout, kh, kw, sh, sw, ph, pw = case
+    x, w, g = _data2d(case, 300 + kh * 7 + cin, integer)
+    gx = to_host(B.sws_conv2d_grad_input(to_gpu(g), to_gpu(w), h, wd, sh, sw, ph, pw))
+    gw = to_host(B.sws_conv2d_grad_weight(to_gpu(x), to_gpu(g), kh, kw, sh, sw, ph, pw))
+    rx, mx = oracle.conv2d_grad_input(g, w, h, wd, sh, sw, ph, pw)
+    rw, mw = oracle.conv2d_grad_weight(x, g, kh, kw, sh, sw, ph, pw)
+    if integer:
+        assert np.array_equal(gx.astype(np.float64), rx) and np.array_equal(gw.astype(np.float64), rw), str(case)
+    else:
+        assert_within_tol(gx, rx, mx, "conv2d grad_input %s" % (case,))
+        assert_within_tol(gw, rw, mw, "conv2d grad_weight %s" % (case,))
+
+
+def test_conv2d_adjoints_direct_evaluation_kernels(B):
+    B.sws_set_option("conv2d_variant", 1)
+    try:
+        test_conv2d_adjoints(B, CASES_2D[0], False)
+        test_conv2d_adjoints(B, CASES_2D[4], True)
+    finally:
+        B.sws_set_option("conv2d_variant", 0)
+
+
+def test_conv2d_adjoints_resnet_layer_slice(B):
+    """Configuration 4's layer (64 -> 64 channels, 3 x 3, pad 1, 56 x 56 planes) on 2 images."""
+    test_conv2d_adjoints(B, (2, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1), False)
