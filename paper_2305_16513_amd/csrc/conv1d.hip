@@ -169,7 +169,7 @@ template <int KB4>
 hipError_t launch_thin(const float *x, const float *wgt, float *y, int64_t rows_out, int L, int Lo, int k, int pad,
                        int Cin, int Cout, int cog, hipStream_t s, int wflip)
 {
-    const int tiles_per_row = (Lo + 15 + kTileOut - 1) / kTileOut;     // origins move back by up to 15
+    const int tiles_per_row = (Lo + max_origin_shift(Lo, 16) + kTileOut - 1) / kTileOut;     // origins move back
     // Tiles per workgroup (measured): two per wavefront while HBM is the bound (the tiles in flight
     // stay a compact window of memory), many once the FMAs dominate (k > 32: fewer prologues).
     int64_t g = (KB4 <= 8 ? 2 : 16) * kWavesPerWg;
@@ -474,7 +474,7 @@ hipError_t launch_thin_dilated(const float *x, const float *wgt, float *y, int64
                                int pad, const DilPlan &pl, int Cin, int Cout, int cog, int cig, hipStream_t s,
                                bool strided = false)
 {
-    const int tiles_per_row = (Lo + 15 + pl.TO - 1) / pl.TO;
+    const int tiles_per_row = (Lo + max_origin_shift(Lo, 16) + pl.TO - 1) / pl.TO;
     int64_t g = (KB4 <= 8 ? 4 : 8) * kWavesPerWg;    // the scatter table is built once per workgroup
     while (g > kWavesPerWg && rows_out * ((tiles_per_row + g - 1) / g) < 2048) g /= 2;   // small problems: more workgroups
     if (g_opt.slide_group > 0) g = g_opt.slide_group;

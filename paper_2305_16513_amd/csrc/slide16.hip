@@ -293,7 +293,7 @@ hipError_t launch_16(const T *x, T *y, int64_t rows, int len, int lo, int w, flo
     if (w >= 2 && w <= kScanMaxW && g_opt.slide_variant != 1) {
         const int S = w - 1;
         const int tout = (kN - S) & ~(kLine - 1);    // a multiple of 64 bytes of y (at least 64 outputs)
-        const int tiles = (lo + kLine - 1 + tout - 1) / tout;
+        const int tiles = (lo + max_origin_shift(lo, kLine) + tout - 1) / tout;
         const int64_t n_tiles = rows * tiles;
         // sixteen tiles per wavefront (measured best: 8 to 32), the next one in flight while one is
         // worked on; workgroups in launch order

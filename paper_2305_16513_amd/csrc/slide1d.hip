@@ -381,7 +381,7 @@ template <int OP>
 hipError_t launch_direct(const float *x, float *y, int64_t rows, int len, int lo, int w, float scale,
                          hipStream_t s)
 {
-    const int tiles_per_row = (lo + 15 + 1023) / 1024;          // origins move back by up to 15
+    const int tiles_per_row = (lo + max_origin_shift(lo, 16) + 1023) / 1024;          // origins move back
     const int64_t n_tiles = rows * tiles_per_row;
     const int64_t n_units = (n_tiles + kWavesPerWg - 1) / kWavesPerWg;
     const int remap = (g_opt.slide_chunk & 8) ? 0 : 1;
@@ -421,7 +421,7 @@ hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, 
     int tout = (lo + tiles - 1) / tiles;
     if (!(opt & 1) && max_tout >= 16) {
         tout = max_tout & ~15;
-        tiles = (lo + 15 + tout - 1) / tout;
+        tiles = (lo + max_origin_shift(lo, 16) + tout - 1) / tout;
         flags |= 4;
         if (!(opt & 2)) flags |= 2;
     }

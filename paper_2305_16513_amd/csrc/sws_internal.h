@@ -67,6 +67,16 @@ __device__ __forceinline__ int64_t xcd_unit(int64_t n_units)
     const int64_t u = (b % kXcd) * per + b / kXcd;
     return (b / kXcd < per && u < n_units) ? u : -1;
 }
+// Kernels pull every row's tile origins back by (r * lo) mod line elements so that stores start on
+// 64-byte lines.  The largest such shift over all rows r: line - gcd(lo mod line, line), i.e. 0 when
+// lo is a multiple of the line (then no row needs an extra tile).
+inline int max_origin_shift(int64_t lo, int line)
+{
+    int a = (int)(lo % line), b = line;
+    while (a) { const int t = b % a; b = a; a = t; }
+    return line - b;
+}
+
 inline int64_t xcd_grid(int64_t n_units) { return ((n_units + kXcd - 1) / kXcd) * kXcd; }
 
 hipError_t launch_copy(const float *src, float *dst, int64_t n, hipStream_t s);
