@@ -146,3 +146,101 @@ def test_slide1d_pair_random(B, seed):
     tol = (w + 24) * 2.0 ** -24
     assert_within_tol(to_host(yu), ru, mu, "seed %d pair u w %d" % (seed, w), tol=tol)
     assert_within_tol(to_host(yv), rv, mv, "seed %d pair v w %d" % (seed, w), tol=tol)
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_slide1d_16_random(B, seed):
+    import torch
+    r = _rng(7500 + seed)
+    w = int(r.choice([1, 2, 3, 5, 9, 16, 17, 33, 64, 100, 255, 256, 511, 850, 961, 1100]))
+    tout = max(32, (1024 - (min(w, 961) - 1)) & ~31)
+    lo = max(1, int(r.integers(1, 8)) * tout + int(r.integers(-40, 41)))
+    rows = int(r.integers(1, 9))
+    x = (r.random((rows, lo + w - 1), dtype=np.float32) * 2 - 1).astype(np.float32)
+    op = int(r.integers(0, 3))
+    tdt, odt, half = ((torch.bfloat16, oracle.DTYPE_BF16, 2.0 ** -8), (torch.float16, oracle.DTYPE_F16, 2.0 ** -11))[seed % 2]
+    xq = torch.from_numpy(x).to(tdt)
+    scale = float(r.choice([1.0, 1.0 / w]))
+    got = B.sws_slide1d_16(op, xq.cuda(), w, scale).cpu().to(torch.float64).numpy()
+    ref, mag = oracle.slide1d(op, xq.to(torch.float32).numpy(), w, scale)
+    what = "seed %d: op %d w %d rows %d lo %d %s" % (seed, op, w, rows, lo, tdt)
+    if op:
+        assert np.array_equal(got, ref), what
+    else:
+        allowed = 1e-5 * mag + (np.abs(ref) + 1e-5 * mag) * half + 2.0 ** -25
+        assert (np.abs(got - ref) <= allowed).all(), what
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_conv1d_adjoints_random(B, seed):
+    r = _rng(7600 + seed)
+    kind = seed % 4
+    if kind == 0:                                   # thin channels
+        c, mult = int(r.integers(1, 7)), int(r.integers(1, 3))
+        cin, cout, groups, k, dil, stride = c, c * mult, c, int(r.integers(1, 70)), int(r.choice([1, 1, 2, 5])), 1
+    elif kind == 1:                                 # dense channels
+        cin, cout, groups = int(r.choice([8, 16, 24, 40, 64, 72])), int(r.integers(1, 80)), 1
+        k, dil, stride = int(r.integers(1, 12)), int(r.choice([1, 1, 2, 3])), 1
+    elif kind == 2:                                 # grouped
+        groups = int(r.integers(2, 5))
+        cin, cout = groups * int(r.integers(2, 6)), groups * int(r.integers(1, 5))
+        k, dil, stride = int(r.integers(1, 20)), int(r.choice([1, 2])), 1
+    else:                                           # strided: direct evaluation
+        groups = int(r.choice([1, 2]))
+        cin, cout = groups * int(r.integers(1, 9)), groups * int(r.integers(1, 9))
+        k, dil, stride = int(r.integers(1, 9)), int(r.choice([1, 2])), int(r.integers(2, 5))
+    span = dil * (k - 1) + 1
+    length = span + int(r.integers(0, 2500))
+    pad = int(r.integers(0, span + 2))
+    b = int(r.integers(1, 4))
+    lo = (length + 2 * pad - span) // stride + 1
+    x = r.standard_normal((b, cin, length), dtype=np.float32)
+    w = (r.standard_normal((cout, cin // groups, k), dtype=np.float32) * np.float32(0.3)).astype(np.float32)
+    g = r.standard_normal((b, cout, lo), dtype=np.float32)
+    what = "seed %d: B %d Cin %d L %d Cout %d k %d stride %d pad %d dil %d groups %d" % (
+        seed, b, cin, length, cout, k, stride, pad, dil, groups)
+    gx = to_host(B.sws_conv1d_grad_input(to_gpu(g), to_gpu(w), length, stride, pad, dil, groups))
+    rx, mx = oracle.conv1d_grad_input(g, w, length, stride, pad, dil, groups)
+    assert_within_tol(gx, rx, mx, "grad_input " + what)
+    gw = to_host(B.sws_conv1d_grad_weight(to_gpu(x), to_gpu(g), k, stride, pad, dil, groups))
+    rw, mw = oracle.conv1d_grad_weight(x, g, k, stride, pad, dil, groups)
+    assert_within_tol(gw, rw, mw, "grad_weight " + what)
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_conv2d_adjoints_random(B, seed):
+    r = _rng(7700 + seed)
+    cin, cout = int(r.choice([3, 8, 16, 24, 40])), int(r.integers(1, 50))
+    kh, kw = int(r.integers(1, 6)), int(r.integers(1, 6))
+    sh, sw = (1, 1) if seed % 3 else (int(r.integers(1, 3)), int(r.integers(1, 3)))
+    ph, pw = int(r.integers(0, kh + 1)), int(r.integers(0, kw + 1))
+    h, wd = kh + int(r.integers(0, 40)), kw + int(r.integers(0, 90))
+    n = int(r.integers(1, 3))
+    ho, wo = (h + 2 * ph - kh) // sh + 1, (wd + 2 * pw - kw) // sw + 1
+    x = r.standard_normal((n, cin, h, wd), dtype=np.float32)
+    w = (r.standard_normal((cout, cin, kh, kw), dtype=np.float32) * np.float32(0.2)).astype(np.float32)
+    g = r.standard_normal((n, cout, ho, wo), dtype=np.float32)
+    what = "seed %d: N %d Cin %d H %d W %d Cout %d k %dx%d s %dx%d p %dx%d" % (seed, n, cin, h, wd, cout, kh, kw, sh, sw, ph, pw)
+    gx = to_host(B.sws_conv2d_grad_input(to_gpu(g), to_gpu(w), h, wd, sh, sw, ph, pw))
+    rx, mx = oracle.conv2d_grad_input(g, w, h, wd, sh, sw, ph, pw)
+    assert_within_tol(gx, rx, mx, "grad_input " + what)
+    gw = to_host(B.sws_conv2d_grad_weight(to_gpu(x), to_gpu(g), kh, kw, sh, sw, ph, pw))
+    rw, mw = oracle.conv2d_grad_weight(x, g, kh, kw, sh, sw, ph, pw)
+    assert_within_tol(gw, rw, mw, "grad_weight " + what)
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_pool2d_ex_random(B, seed):
+    r = _rng(7800 + seed)
+    kh, kw, sh, sw = [(3, 3, 1, 1), (3, 3, 2, 2), (2, 2, 2, 2), (5, 5, 1, 1), (7, 7, 1, 1), (4, 2, 3, 1)][seed % 6]
+    pads = tuple(int(r.integers(0, lim)) for lim in (kh, kw, kh, kw))
+    h, wd = kh + int(r.integers(0, 120)), kw + int(r.integers(0, 150))
+    x = r.standard_normal((int(r.integers(1, 3)), int(r.integers(1, 6)), h, wd), dtype=np.float32)
+    op, div = int(r.integers(0, 3)), int(r.integers(0, 2))
+    y = to_host(B.sws_pool2d_ex(op, to_gpu(x), kh, kw, sh, sw, pads, div if op == 0 else 0, 0.25))
+    ref, mag = oracle.pool2d_ex(op, x, kh, kw, sh, sw, pads, bool(div) and op == 0, 0.25)
+    what = "seed %d: %dx%d s%dx%d pads %s plane %dx%d op %d div %d" % (seed, kh, kw, sh, sw, pads, h, wd, op, div)
+    if op == 0:
+        assert_within_tol(y, ref, mag, what)
+    else:
+        assert_bit_exact(y, ref, what)
