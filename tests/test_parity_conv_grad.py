@@ -190,3 +190,50 @@ def test_conv2d_adjoints_direct_evaluation_kernels(B):
 def test_conv2d_adjoints_resnet_layer_slice(B):
     """Configuration 4's layer (64 -> 64 channels, 3 x 3, pad 1, 56 x 56 planes) on 2 images."""
     test_conv2d_adjoints(B, (2, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1), False)
+
+
+def test_graph_replay_of_the_adjoints_and_the_16_bit_sums(B):
+    """The newer entry points also only enqueue kernels (gw is cleared by a fill kernel, not a
+    memset): captured in a HIP graph and replayed with eager work between the replays they must give
+    the eager results — bit for bit except gw, whose atomic adds land in no fixed order (small-integer
+    data makes that exact too)."""
+    import torch
+    case = (2, 16, 1500, 24, 3, 1, 1, 1, 1)
+    x, w, g = _data(case, 5, integer=True)
+    xd, wd, gd = to_gpu(x), to_gpu(w), to_gpu(g)
+    x16 = xd.to(torch.bfloat16)
+    gx = torch.empty_like(xd)
+    gw = torch.empty_like(wd)
+    y16 = torch.empty(2, 16, 1500 - 63, device="cuda", dtype=torch.bfloat16)
+    pe = torch.empty(2, 16, 750, 1, device="cuda")
+
+    def launch_all():
+        B.sws_conv1d_grad_input(gd, wd, 1500, 1, 1, 1, 1, gx=gx)
+        B.sws_conv1d_grad_weight(xd, gd, 3, 1, 1, 1, 1, gw=gw)
+        B.sws_slide1d_16(1, x16, 64, 1.0, y=y16)
+        B.sws_pool2d_ex(0, xd.view(2, 16, 1500, 1), 3, 1, 2, 1, (1, 0, 1, 0), B.SWS_DIV_REAL_CELLS, 1.0, y=pe)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        launch_all()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        launch_all()
+    for rep in range(3):
+        gd.copy_(to_gpu(workloads.integer_valued(g.shape, -3, 3, 50 + rep)))      # eager work between replays
+        for t in (gx, gw, pe):
+            t.fill_(7.0)
+        y16.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (gx, gw, y16, pe)]
+        launch_all()
+        torch.cuda.synchronize()
+        for a, b in zip(got, (gx, gw, y16, pe)):
+            assert torch.equal(a, b), "replay %d differs from the eager result" % rep
+        ref, _ = oracle.conv1d_grad_weight(x, to_host(gd), 3, 1, 1, 1, 1)
+        assert np.array_equal(to_host(got[1]).astype(np.float64), ref)
