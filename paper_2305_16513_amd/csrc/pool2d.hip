@@ -202,6 +202,159 @@ hipError_t launch_band(const float *x, float *y, int64_t planes, int H, int W, i
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------
+// Any window, stride and padding: the same separable evaluation with the geometry at run time.
+// A wavefront stages the input rows of a band of TH output rows, reduces them down H into a
+// second LDS array (one row per output row, kh combines per column), then reduces along W from
+// there (kw combines per output): kh + kw combines per output where direct evaluation does kh*kw,
+// and HBM still sees one read of x and one write of y.
+// ------------------------------------------------------------------------------------------------
+constexpr int kSepLds = 12 * 1024;                   // bytes of LDS per wavefront
+
+template <int OP>
+__global__ __launch_bounds__(kThreads) void pool2d_sep_kernel(const float *__restrict__ x, float *__restrict__ y, int H,
+                                                              int W, int Ho, int Wo, int kh, int kw, int sh, int sw,
+                                                              int ph, int pw, int P, int PC, int pwl, int TH, int bands,
+                                                              float scale, int64_t n_units, int lds_floats,
+                                                              int in_rows, int div_valid)
+{
+    using O = Op<OP>;
+    extern __shared__ __attribute__((aligned(16))) float lds_all[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
+    if (unit >= n_units) return;
+    // in:  [in_rows][P]  the input rows hv0 .. hv0 + in_rows - 1 of the band, rows outside the plane
+    //                    (and columns W .. P-1) holding the identity, so that the loop over kh needs no bounds
+    // col: [TH][PC]      those rows reduced down H, with pwl identity columns in front and enough
+    //                    behind that the loop over kw needs none either
+    float *in = lds_all + wave * lds_floats;
+    float *col = in + in_rows * P;
+    const int64_t plane = unit / bands;
+    const int band = (int)(unit - plane * bands);
+    const float *xp = x + plane * (int64_t)H * W;
+    float *yp = y + plane * (int64_t)Ho * Wo;
+    const int ho0 = band * TH;
+    int ho1 = ho0 + TH;
+    if (ho1 > Ho) ho1 = Ho;
+    const int nr = ho1 - ho0;
+    const int hv0 = ho0 * sh - ph;                   // first (possibly virtual) input row of the band
+    const int rows_need = (nr - 1) * sh + kh;
+    int row_lo = hv0 < 0 ? 0 : hv0, row_hi = hv0 + rows_need > H ? H : hv0 + rows_need;
+    const int P4 = P >> 2;
+    const float inv_p4 = 1.0f / (float)P4;
+    const v4f id4 = {O::id(), O::id(), O::id(), O::id()};
+    // ---- stage: identity rows above and below the plane, then the real rows
+    for (int i = lane; i < (row_lo - hv0) * P4; i += kWave) *(v4f *)(in + 4 * i) = id4;
+    for (int i = (row_hi - hv0) * P4 + lane; i < rows_need * P4; i += kWave) *(v4f *)(in + 4 * i) = id4;
+    float *in_real = in + (row_lo - hv0) * P;
+    if (P == W) {
+        // the real rows are one contiguous range: all its 128-bit loads are issued before the first
+        // LDS write (lanes past the end re-read element 0 and drop it)
+        const float *src = xp + (int64_t)row_lo * W;
+        const int n4 = (row_hi - row_lo) * P4;
+        constexpr int NL = kSepLds / 16 / kWave;
+        v4f g4[NL];
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            const int i = lane + kWave * j;
+            g4[j] = *(const v4f_u *)(src + (i < n4 ? 4 * i : 0));
+        }
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            const int i = lane + kWave * j;
+            if (i < n4) *(v4f *)(in_real + 4 * i) = g4[j];
+        }
+    } else {
+        const int n = (row_hi - row_lo) * P;
+        const float inv_p = 1.0f / (float)P;
+        for (int i = lane; i < n; i += kWave) {
+            const int r = (int)(((float)i + 0.5f) * inv_p), c = i - r * P;
+            in_real[i] = (c < W) ? xp[(int64_t)(row_lo + r) * W + c] : O::id();
+        }
+    }
+    // identity margins of col: pwl columns in front, PC - pwl - P behind
+    const int mr = PC - pwl - P;
+    for (int i = lane; i < nr * (pwl + mr); i += kWave) {
+        const int r = i / (pwl + mr), c = i - r * (pwl + mr);
+        col[r * PC + (c < pwl ? c : P + c)] = O::id();
+    }
+    wave_lds_sync();
+    // ---- down H: col[r][pwl + c] = (+)_{a < kh} in[r*sh + a][c], four columns per item
+    for (int item = lane; item < nr * P4; item += kWave) {
+        const int r = (int)(((float)item + 0.5f) * inv_p4), g = item - r * P4;
+        const float *p = in + r * sh * P + 4 * g;
+        v4f acc = *(const v4f *)p;
+        int a = 1;
+#define SWS_ACC4(v) acc.x = O::f(acc.x, v.x); acc.y = O::f(acc.y, v.y); acc.z = O::f(acc.z, v.z); acc.w = O::f(acc.w, v.w)
+        for (; a + 4 <= kh; a += 4) {                // four reads in flight per wait
+            const v4f v0 = *(const v4f *)(p + a * P), v1 = *(const v4f *)(p + (a + 1) * P);
+            const v4f v2 = *(const v4f *)(p + (a + 2) * P), v3 = *(const v4f *)(p + (a + 3) * P);
+            SWS_ACC4(v0); SWS_ACC4(v1); SWS_ACC4(v2); SWS_ACC4(v3);
+        }
+        for (; a < kh; ++a) {
+            const v4f v = *(const v4f *)(p + a * P);
+            SWS_ACC4(v);
+        }
+#undef SWS_ACC4
+        *(v4f *)(col + r * PC + pwl + 4 * g) = acc;
+    }
+    wave_lds_sync();
+    // ---- along W: one output per lane, consecutive lanes on consecutive outputs (their LDS reads
+    //      fall on consecutive banks, their stores on one contiguous run of y)
+    const float inv_wo = 1.0f / (float)Wo;
+    for (int item = lane; item < nr * Wo; item += kWave) {
+        const int r = (int)(((float)item + 0.5f) * inv_wo), wo = item - r * Wo;
+        const float *cr = col + r * PC + pwl - pw + wo * sw;
+        float acc = cr[0];
+        int b = 1;
+        for (; b + 4 <= kw; b += 4) {                // four reads in flight per wait
+            const float v0 = cr[b], v1 = cr[b + 1], v2 = cr[b + 2], v3 = cr[b + 3];
+            acc = O::f(O::f(O::f(O::f(acc, v0), v1), v2), v3);
+        }
+        for (; b < kw; ++b) acc = O::f(acc, cr[b]);
+        const int ho = ho0 + r;
+        if (OP == SWS_OP_ADD) {
+            float sc = scale;
+            if (div_valid) {                         // real cells of this window
+                const int h0 = ho * sh - ph, c0 = wo * sw - pw;
+                const int rows_in = (h0 + kh < H ? h0 + kh : H) - (h0 > 0 ? h0 : 0);
+                const int cols_in = (c0 + kw < W ? c0 + kw : W) - (c0 > 0 ? c0 : 0);
+                sc = scale / (float)(rows_in * cols_in);
+            }
+            acc *= sc;
+        }
+        __builtin_nontemporal_store(acc, yp + (int64_t)ho * Wo + wo);
+    }
+}
+
+template <int OP>
+hipError_t launch_sep(const float *x, float *y, int64_t planes, int H, int W, int Ho, int Wo, int kh, int kw, int sh,
+                      int sw, int ph, int pw, float scale, int div_valid, hipStream_t s, bool *taken)
+{
+    const int P = (W + 3) / 4 * 4;
+    const int pwl = (pw + 3) / 4 * 4;                // identity columns in front of a reduced row (kept 16-byte aligned)
+    int right = (Wo - 1) * sw - pw + kw - P;         // columns a window reaches beyond the staged pitch
+    if (right < 0) right = 0;
+    const int PC = pwl + P + (right + 3) / 4 * 4;
+    // output rows per band: as many as the slice holds — (TH-1)*sh + kh staged rows of P floats plus
+    // TH reduced rows of PC floats
+    const int budget = kSepLds / 4;
+    int TH = (budget - (kh - sh) * P) / (sh * P + PC);
+    if (TH > Ho) TH = Ho;
+    *taken = TH >= 1 && (int64_t)Ho * Wo < (1 << 20) && (int64_t)H * P < (1 << 20);
+    if (!*taken) return hipSuccess;
+    const int in_rows = (TH - 1) * sh + kh;
+    const int lds_floats = in_rows * P + TH * PC;
+    const int bands = (Ho + TH - 1) / TH;
+    const int64_t n_units = planes * bands;
+    const int64_t grid = (n_units + kWaves - 1) / kWaves;
+    if (grid > 2147483647LL) { *taken = false; return hipSuccess; }
+    hipLaunchKernelGGL((pool2d_sep_kernel<OP>), dim3((unsigned)grid), dim3(kThreads), (size_t)lds_floats * 4 * kWaves, s,
+                       x, y, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, P, PC, pwl, TH, bands, scale, n_units, lds_floats,
+                       in_rows, div_valid);
+    return hipGetLastError();
+}
+
 template <int OP>
 hipError_t dispatch_band(const float *x, float *y, int64_t planes, int H, int W, int Ho, int Wo, int kh, int kw,
                          int sh, int sw, int ph, int pw, float scale, int div_valid, hipStream_t s, bool *taken)
@@ -248,6 +401,22 @@ hipError_t launch_pool2d(int op, const float *x, float *y, int64_t planes, int64
         default:
             e = dispatch_band<SWS_OP_MIN>(x, y, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw,
                                           scale, div_valid, s, &taken);
+            break;
+        }
+        if (taken) return e;
+        // no specialised kernel for this geometry: the run-time separable kernel
+        switch (op) {
+        case SWS_OP_ADD:
+            e = launch_sep<SWS_OP_ADD>(x, y, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw, scale,
+                                       div_valid, s, &taken);
+            break;
+        case SWS_OP_MAX:
+            e = launch_sep<SWS_OP_MAX>(x, y, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw, scale,
+                                       div_valid, s, &taken);
+            break;
+        default:
+            e = launch_sep<SWS_OP_MIN>(x, y, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw, scale,
+                                       div_valid, s, &taken);
             break;
         }
         if (taken) return e;

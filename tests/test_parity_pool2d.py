@@ -33,6 +33,9 @@ GEOMS = [
     (3, 3, 1, 1, 1, 1), (3, 3, 2, 2, 1, 1), (3, 3, 1, 1, 0, 0), (2, 2, 2, 2, 0, 0), (5, 5, 1, 1, 2, 2),
     (3, 5, 1, 2, 1, 2), (7, 2, 3, 1, 3, 0), (1, 1, 1, 1, 0, 0), (1, 4, 1, 1, 0, 3), (4, 1, 2, 1, 3, 0),
     (13, 13, 1, 1, 6, 6), (3, 3, 3, 3, 0, 0), (9, 9, 1, 1, 4, 4), (7, 7, 1, 1, 3, 3), (2, 2, 1, 1, 0, 0),
+    # no specialised kernel: the run-time separable kernel
+    (11, 11, 1, 1, 5, 5), (4, 4, 4, 4, 0, 0), (6, 6, 2, 2, 2, 2), (15, 15, 1, 1, 7, 7), (1, 7, 1, 1, 0, 3), (16, 3, 5, 2, 8, 1),
+    (3, 31, 1, 4, 2, 15),
 ]
 
 
