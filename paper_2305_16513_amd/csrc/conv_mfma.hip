@@ -264,7 +264,8 @@ struct SegPlan {
 };
 
 // (the second launch bound is wavefronts per SIMD: two workgroups per compute unit)
-template <int KTT, int WAVES, int NB, int SEG>
+// TAIL: the input-channel count is not a multiple of 8; channels beyond it are staged as zeros.
+template <int KTT, int WAVES, int NB, int SEG, bool TAIL = false>
 __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c8_kernel(const float *__restrict__ x,
                                                                        const float *__restrict__ wgt,
                                                                        float *__restrict__ y, ConvGeom g,
@@ -330,13 +331,14 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
 
     // ---- input staging plan: slot s of this wavefront moves segment wave + 8*s
     const int nseg = CIB * g.NRows * g.CH;
-    int xg[XS], xl[XS];
+    int xg[XS], xl[XS], xc[XS];
 #pragma unroll
     for (int s = 0; s < XS; ++s) {
         const int seg = wave + WAVES * s;
         const int sq = seg < MAXSEG ? seg : MAXSEG - 1;
         const unsigned int pe = sp.e[sq];             // uniform index: a scalar load
         const int ci = pe & 255, rr = (pe >> 8) & 255, ch = pe >> 16;
+        xc[s] = ci;
         const int gh = row0 + rr, cc = ch * 64 + lane, gw = col0 + cc;
         const bool act = seg < nseg && cc < g.Wt;
         xl[s] = act ? (rr * g.Wt + cc) * XP + ci : -1;
@@ -366,30 +368,37 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
     auto prefetch = [&](int ci0) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            const int xb = (ci0 + nb * CIB) * plane;
-#pragma unroll
-            for (int s = 0; s < XS; ++s) xreg[nb][s] = xn[xg[s] >= 0 ? xb + xg[s] : 0];
-            const float *w = wsrc + (w_ok ? (ci0 + nb * CIB) * w_sci : 0);
-#pragma unroll
-            for (int t = 0; t < KTMAX; ++t) wreg[nb][t] = w[(t < KT ? t : 0) * w_st];
-        }
-    };
-    auto commit = [&]() {
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
+            const int cb = ci0 + nb * CIB;            // first channel of this block
+            const int xb = cb * plane;
 #pragma unroll
             for (int s = 0; s < XS; ++s)
-                if (xl[s] >= 0) Xl[nb * g.CP + xl[s]] = xg[s] >= 0 ? xreg[nb][s] : 0.0f;
+                xreg[nb][s] = xn[(xg[s] >= 0 && (!TAIL || cb + xc[s] < g.Cin)) ? xb + xg[s] : 0];
+            const bool wk = w_ok && (!TAIL || cb + w_ci < g.Cin);
+            const float *w = wk ? wsrc + cb * w_sci : wgt;
+            const int st = wk ? w_st : 0;
+#pragma unroll
+            for (int t = 0; t < KTMAX; ++t) wreg[nb][t] = w[(t < KT ? t : 0) * st];
+        }
+    };
+    auto commit = [&](int ci0) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int cb = ci0 + nb * CIB;
+#pragma unroll
+            for (int s = 0; s < XS; ++s)
+                if (xl[s] >= 0)
+                    Xl[nb * g.CP + xl[s]] = (xg[s] >= 0 && (!TAIL || cb + xc[s] < g.Cin)) ? xreg[nb][s] : 0.0f;
+            const bool wk = w_ok && (!TAIL || cb + w_ci < g.Cin);
 #pragma unroll
             for (int t = 0; t < KTMAX; ++t)
-                if (t < KT && w_mine) wdst[nb * wblock + t * kCoTile * XP] = w_ok ? wreg[nb][t] : 0.0f;
+                if (t < KT && w_mine) wdst[nb * wblock + t * kCoTile * XP] = wk ? wreg[nb][t] : 0.0f;
         }
     };
 
     prefetch(0);
     for (int ci0 = 0; ci0 < g.Cin; ci0 += CIB * NB) {
         __syncthreads();                              // the previous blocks have been consumed
-        commit();
+        commit(ci0);
         __syncthreads();
         if (ci0 + CIB * NB < g.Cin) prefetch(ci0 + CIB * NB);   // in flight during the matrix work below
         if (!useful) continue;                        // a block of 32 output channels beyond Cout: staging only
@@ -488,10 +497,10 @@ struct C8Launch {
     SegPlan sp;
     dim3 grid;
     size_t lds;
-    int waves, ktt, nb, seg;
+    int waves, ktt, nb, seg, tail;
 };
 
-// Decides tile width and template instance for the geometry in L->g (kh * kw <= 9, Cin % 8 == 0).
+// Decides tile width and template instance for the geometry in L->g (kh * kw <= 9).
 bool c8_prepare(C8Launch *L, int64_t N)
 {
     ConvGeom &g = L->g;
@@ -530,7 +539,8 @@ bool c8_prepare(C8Launch *L, int64_t N)
     L->grid = dim3((unsigned)g.tiles_per_img, (unsigned)g.co_blocks, (unsigned)N);
     L->lds = (nb4 ? 4 : 1) * lds1;
     L->waves = seg128 ? 8 : best_w;
-    L->ktt = (KT == 9 && g.kw == 3) ? 9 : ((KT == 3 && g.kw == 3) ? 3 : 0);
+    L->tail = g.Cin % 8 != 0;                         // generic-tap instances only (fewer kernels to build)
+    L->ktt = L->tail ? 0 : ((KT == 9 && g.kw == 3) ? 9 : ((KT == 3 && g.kw == 3) ? 3 : 0));
     L->nb = (nb4 && !seg128) ? 4 : 1;
     L->seg = seg128 ? 128 : (L->nb == 4 ? 32 : 64);
     return true;
@@ -547,7 +557,18 @@ hipError_t c8_launch(const C8Launch &L, const float *x, const float *wgt, float 
     case 12: SWS_C8(KTT, 12, NB, SEG); break;                                                                   \
     default: SWS_C8(KTT, 14, NB, SEG); break;                                                                   \
     }
-    if (L.seg == 128) {
+    if (L.tail) {
+#define SWS_C8T(WV, SEG)                                                                                        \
+    hipLaunchKernelGGL((conv2d_mfma_c8_kernel<0, WV, 1, SEG, true>), L.grid, dim3(WV * 64), L.lds, s, x, wgt, y, L.g, L.sp)
+        if (L.seg == 128) SWS_C8T(8, 128);
+        else switch (L.waves) {
+            case 8: SWS_C8T(8, 64); break;
+            case 10: SWS_C8T(10, 64); break;
+            case 12: SWS_C8T(12, 64); break;
+            default: SWS_C8T(14, 64); break;
+        }
+#undef SWS_C8T
+    } else if (L.seg == 128) {
         if (L.ktt == 9) SWS_C8(9, 8, 1, 128);
         else if (L.ktt == 3) SWS_C8(3, 8, 1, 128);
         else SWS_C8(0, 8, 1, 128);
@@ -588,8 +609,11 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
     // Up to 36 adjacent taps at stride 1 the scalar-read kernel does the whole kernel in one pass,
     // which beats a chain of five or more launches (5 x 5 on [32,64,56,56]: 0.27 ms against 0.41 ms).
     const bool one_pass = !wadj && plain && KT > 9 && KT <= 36 && Cin % 4 == 0 && g_opt.conv2d_variant != 6;
-    // preferred: channel-fastest tiles with 128-bit operand reads (Cin % 8 == 0)
-    if (!one_pass && Cin % 8 == 0 && g_opt.conv2d_variant != 3 && g_opt.conv2d_variant != 4 &&
+    // preferred: channel-fastest tiles with 128-bit operand reads (8 input channels per block; a last
+    // partial block is padded with zeros)
+    // Cin = 4, 12, 20, ... at stride 1: the scalar-read kernel with blocks of 4 channels wastes none
+    const bool quad_blocks = Cin % 8 != 0 && Cin % 4 == 0 && plain && !wadj && KT <= 36;
+    if (!one_pass && !quad_blocks && g_opt.conv2d_variant != 3 && g_opt.conv2d_variant != 4 &&
         (KT <= 9 || kh == 1 || kw <= 9)) {
         // chunks of at most 9 taps: runs of a one-row kernel, or whole rows of a taller one
         const bool along_w = KT > 9 && kh == 1;
