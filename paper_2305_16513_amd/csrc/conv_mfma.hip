@@ -613,23 +613,23 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
     // partial block is padded with zeros)
     // Cin = 4, 12, 20, ... at stride 1: the scalar-read kernel with blocks of 4 channels wastes none
     const bool quad_blocks = Cin % 8 != 0 && Cin % 4 == 0 && plain && !wadj && KT <= 36;
-    if (!one_pass && !quad_blocks && g_opt.conv2d_variant != 3 && g_opt.conv2d_variant != 4 &&
-        (KT <= 9 || kh == 1 || kw <= 9)) {
-        // chunks of at most 9 taps: runs of a one-row kernel, or whole rows of a taller one
-        const bool along_w = KT > 9 && kh == 1;
-        const int per = KT <= 9 ? (along_w ? kw : kh) : (along_w ? 9 : 9 / kw);      // taps / rows per chunk
-        const int total = along_w ? kw : kh;
-        const int n_chunks = KT <= 9 ? 1 : (total + per - 1) / per;
+    if (!one_pass && !quad_blocks && g_opt.conv2d_variant != 3 && g_opt.conv2d_variant != 4) {
+        // chunks of at most 9 taps: the whole kernel, whole rows of it (rows of up to 9 taps), or
+        // runs of up to 9 taps of one row (wider rows)
+        const int rows_per = KT <= 9 ? kh : (kw <= 9 ? 9 / kw : 1);
+        const int taps_per = kw <= 9 ? kw : 9;
+        const int row_chunks = (kh + rows_per - 1) / rows_per, run_chunks = (kw + taps_per - 1) / taps_per;
+        const int n_chunks = row_chunks * run_chunks;
         if (n_chunks <= 64) {
             C8Launch L[64];
             bool ok = true;
             for (int c = 0; c < n_chunks && ok; ++c) {
-                const int first = c * per, cnt = (total - first < per) ? total - first : per;
+                const int a0 = (c / run_chunks) * rows_per, b0 = (c % run_chunks) * taps_per;
+                const int na = kh - a0 < rows_per ? kh - a0 : rows_per, nb = kw - b0 < taps_per ? kw - b0 : taps_per;
                 L[c].g = g;
-                if (KT > 9) {
-                    if (along_w) { L[c].g.kw = cnt; L[c].g.pw = pw - first * dw; L[c].g.wofs = first; }
-                    else { L[c].g.kh = cnt; L[c].g.ph = ph - first * dh; L[c].g.wofs = first * kw; }
-                }
+                L[c].g.kh = na; L[c].g.ph = ph - a0 * dh;
+                L[c].g.kw = nb; L[c].g.pw = pw - b0 * dw;
+                L[c].g.wofs = a0 * kw + b0;           // a chunk of several rows takes whole rows: its taps stay contiguous
                 L[c].g.accum = c > 0;
                 ok = c8_prepare(&L[c], N);
             }

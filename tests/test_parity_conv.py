@@ -261,6 +261,26 @@ def test_conv2d_chunks_of_kernel_rows(B, cin, cout, kh, kw, ph, pw):
         B.sws_set_option("conv2d_variant", 0)
 
 
+@pytest.mark.parametrize("cin,cout,kh,kw,h,w_,sh,sw,ph,pw", [
+    (3, 64, 7, 7, 64, 64, 2, 2, 3, 3),       # a ResNet stem: three input channels (a zero-padded channel block), seven row chunks
+    (3, 24, 11, 11, 67, 67, 4, 4, 2, 2),     # an AlexNet stem: rows wider than 9 taps -> runs of taps of each row
+    (16, 16, 2, 12, 20, 50, 1, 1, 1, 6),     # two rows of twelve taps
+    (5, 7, 3, 3, 19, 23, 1, 1, 1, 1),        # odd channel counts on both sides
+    (13, 9, 1, 1, 10, 10, 1, 1, 0, 0),
+    (12, 8, 3, 10, 15, 40, 2, 1, 1, 0),      # 12 channels with strides: no block-of-4 kernel
+])
+def test_conv2d_any_channel_count_and_wide_kernels(B, cin, cout, kh, kw, h, w_, sh, sw, ph, pw):
+    r = _rng(cin * 3 + cout + kh * 11 + kw)
+    x = r.standard_normal((2, cin, h, w_), dtype=np.float32)
+    w = (r.standard_normal((cout, cin, kh, kw), dtype=np.float32) * np.sqrt(2.0 / (cin * kh * kw))).astype(np.float32)
+    _c2(B, x, w, sh, sw, ph, pw, what=str((cin, cout, kh, kw, h, w_, sh, sw, ph, pw)))
+    xi = workloads.integer_valued((1, cin, h, w_), -3, 3, cin + kh)
+    wi = workloads.integer_valued((cout, cin, kh, kw), -2, 2, cout + kw)
+    y = to_host(B.sws_conv2d(to_gpu(xi), to_gpu(wi), sh, sw, ph, pw))
+    ref, _ = oracle.conv2d(xi, wi, sh, sw, ph, pw)
+    assert np.array_equal(y.astype(np.float64), ref)
+
+
 @pytest.mark.parametrize("variant", [1, 3, 8, 10, 12, 14])
 def test_conv2d_variants_agree_with_oracle(B, variant):
     """The direct-evaluation kernel (1), the 4-wavefront scalar-read matrix kernel (3), and the
