@@ -264,8 +264,10 @@ struct SegPlan {
 };
 
 // (the second launch bound is wavefronts per SIMD: two workgroups per compute unit)
-// TAIL: the input-channel count is not a multiple of 8; channels beyond it are staged as zeros.
-template <int KTT, int WAVES, int NB, int SEG, bool TAIL = false>
+// GEN: the general instance — the input-channel count need not be a multiple of 8 (channels beyond
+// it are staged as zeros) and the weights may be read through the adjoint view.  The plain
+// instance keeps constant tap offsets and unguarded channel blocks.
+template <int KTT, int WAVES, int NB, int SEG, bool GEN = false>
 __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c8_kernel(const float *__restrict__ x,
                                                                        const float *__restrict__ wgt,
                                                                        float *__restrict__ y, ConvGeom g,
@@ -353,10 +355,12 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
     // Plain view: wgt[co][ci][wofs + t].  Adjoint view (the convolution that maps output gradients
     // back to the input): this launch's output channel co is the stored array's input channel, so
     // the element is wgt[ci][co][wstride - 1 - wofs - t] with rows of g.Cout pairs.
-    const int64_t w_sci = g.wadj ? (int64_t)g.Cout * g.wstride : g.wstride;
-    const int w_st = w_ok ? (g.wadj ? -1 : 1) : 0;   // threads without a pair re-read element 0
-    const float *wsrc = wgt + (w_ok ? (g.wadj ? (int64_t)w_ci * w_sci + (int64_t)(co0 + w_co) * g.wstride + g.wstride - 1 - g.wofs
-                                              : ((int64_t)(co0 + w_co) * g.Cin + w_ci) * g.wstride + g.wofs)
+    constexpr bool TAIL = GEN;
+    const bool adj = GEN && g.wadj;
+    const int64_t w_sci = adj ? (int64_t)g.Cout * g.wstride : g.wstride;
+    const int w_st = GEN ? (w_ok ? (adj ? -1 : 1) : 0) : 1;   // threads without a pair re-read element 0
+    const float *wsrc = wgt + (w_ok ? (adj ? (int64_t)w_ci * w_sci + (int64_t)(co0 + w_co) * g.wstride + g.wstride - 1 - g.wofs
+                                           : ((int64_t)(co0 + w_co) * g.Cin + w_ci) * g.wstride + g.wofs)
                                     : 0);
     float *wdst = Wl + w_co * XP + w_ci;
 
@@ -373,11 +377,17 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
 #pragma unroll
             for (int s = 0; s < XS; ++s)
                 xreg[nb][s] = xn[(xg[s] >= 0 && (!TAIL || cb + xc[s] < g.Cin)) ? xb + xg[s] : 0];
-            const bool wk = w_ok && (!TAIL || cb + w_ci < g.Cin);
-            const float *w = wk ? wsrc + cb * w_sci : wgt;
-            const int st = wk ? w_st : 0;
+            if constexpr (GEN) {
+                const bool wk = w_ok && cb + w_ci < g.Cin;
+                const float *w = wk ? wsrc + cb * w_sci : wgt;
+                const int st = wk ? w_st : 0;
 #pragma unroll
-            for (int t = 0; t < KTMAX; ++t) wreg[nb][t] = w[(t < KT ? t : 0) * st];
+                for (int t = 0; t < KTMAX; ++t) wreg[nb][t] = w[(t < KT ? t : 0) * st];
+            } else {
+                const float *w = wsrc + (w_ok ? cb * g.wstride : 0);
+#pragma unroll
+                for (int t = 0; t < KTMAX; ++t) wreg[nb][t] = w[t < KT ? t : 0];
+            }
         }
     };
     auto commit = [&](int ci0) {
@@ -528,7 +538,8 @@ bool c8_prepare(C8Launch *L, int64_t N)
     const int xfloats = (g.NRows * g.Wt * 12 + 3) / 4 * 4;
     const size_t lds1 = 4 * ((size_t)xfloats + (size_t)KT * kCoTile * 12);
     // few taps: four channel blocks per barrier pair, if they fit
-    const bool nb4 = KT == 3 && g.kw == 3 && g.Cin % 32 == 0 && 8 * g.NRows * g.CH <= 32 && 4 * lds1 <= 64 * 1024 &&
+    const bool general = g.Cin % 8 != 0 || g.wadj;    // the general instance stages one channel block per barrier pair
+    const bool nb4 = !general && KT == 3 && g.kw == 3 && g.Cin % 32 == 0 && 8 * g.NRows * g.CH <= 32 && 4 * lds1 <= 64 * 1024 &&
                      g_opt.conv2d_variant != 5;
     const bool seg128 = 8 * g.NRows * g.CH > 64;          // only reached with 8 wavefronts (strided: tall tiles)
     g.CP = xfloats;
@@ -539,8 +550,8 @@ bool c8_prepare(C8Launch *L, int64_t N)
     L->grid = dim3((unsigned)g.tiles_per_img, (unsigned)g.co_blocks, (unsigned)N);
     L->lds = (nb4 ? 4 : 1) * lds1;
     L->waves = seg128 ? 8 : best_w;
-    L->tail = g.Cin % 8 != 0;                         // generic-tap instances only (fewer kernels to build)
-    L->ktt = L->tail ? 0 : ((KT == 9 && g.kw == 3) ? 9 : ((KT == 3 && g.kw == 3) ? 3 : 0));
+    L->tail = general;
+    L->ktt = (KT == 9 && g.kw == 3) ? 9 : ((KT == 3 && g.kw == 3) ? 3 : 0);
     L->nb = (nb4 && !seg128) ? 4 : 1;
     L->seg = seg128 ? 128 : (L->nb == 4 ? 32 : 64);
     return true;
@@ -557,16 +568,21 @@ hipError_t c8_launch(const C8Launch &L, const float *x, const float *wgt, float 
     case 12: SWS_C8(KTT, 12, NB, SEG); break;                                                                   \
     default: SWS_C8(KTT, 14, NB, SEG); break;                                                                   \
     }
-    if (L.tail) {
-#define SWS_C8T(WV, SEG)                                                                                        \
-    hipLaunchKernelGGL((conv2d_mfma_c8_kernel<0, WV, 1, SEG, true>), L.grid, dim3(WV * 64), L.lds, s, x, wgt, y, L.g, L.sp)
-        if (L.seg == 128) SWS_C8T(8, 128);
-        else switch (L.waves) {
-            case 8: SWS_C8T(8, 64); break;
-            case 10: SWS_C8T(10, 64); break;
-            case 12: SWS_C8T(12, 64); break;
-            default: SWS_C8T(14, 64); break;
-        }
+    if (L.tail) {                                     // the general instance: one channel block per barrier pair
+#define SWS_C8T(KTT, WV, SEG)                                                                                   \
+    hipLaunchKernelGGL((conv2d_mfma_c8_kernel<KTT, WV, 1, SEG, true>), L.grid, dim3(WV * 64), L.lds, s, x, wgt, y, L.g, L.sp)
+#define SWS_C8T_W(KTT)                                                                                          \
+    if (L.seg == 128) SWS_C8T(KTT, 8, 128);                                                                     \
+    else switch (L.waves) {                                                                                     \
+        case 8: SWS_C8T(KTT, 8, 64); break;                                                                     \
+        case 10: SWS_C8T(KTT, 10, 64); break;                                                                   \
+        case 12: SWS_C8T(KTT, 12, 64); break;                                                                   \
+        default: SWS_C8T(KTT, 14, 64); break;                                                                   \
+    }
+        if (L.ktt == 9) { SWS_C8T_W(9) }
+        else if (L.ktt == 3) { SWS_C8T_W(3) }
+        else { SWS_C8T_W(0) }
+#undef SWS_C8T_W
 #undef SWS_C8T
     } else if (L.seg == 128) {
         if (L.ktt == 9) SWS_C8(9, 8, 1, 128);
