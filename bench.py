@@ -271,6 +271,17 @@ def sweeps_table(torch, B, workloads, iters=20):
         del xs
     del x16
     torch.cuda.empty_cache()
+    x3 = g(workloads.make(3)[0]).to(torch.bfloat16)       # configuration 3's pooling on bf16 storage
+    for st, ho in ((1, 112), (2, 56)):
+        y = torch.empty(32, 64, ho, ho, device="cuda", dtype=torch.bfloat16)
+        nb = 2 * 2048 * (112 * 112 + ho * ho)
+        for op, opn in ((1, "max"), (0, "avg")):
+            ms = time_launches(torch, lambda: B.sws_pool2d_16(op, x3, 3, 3, st, st, 1, 1, 1.0 / 9, y=y), iters)
+            out["storage_16bit"]["bf16_%spool3x3_s%d" % (opn, st)] = {
+                "us": round(ms * 1e3, 2), "GBps": round(nb / ms / 1e6, 1), "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+        del y
+    del x3
+    torch.cuda.empty_cache()
     # the adjoints of the sliding dot product (training): configuration 5's depthwise layer (HBM-bound:
     # grad-input moves what the forward pass moves, grad-weight reads x and gy) and configuration 2's
     # dense layer (matrix cores; 2*Cin*k FLOP per output element for either adjoint)

@@ -130,6 +130,15 @@ sws_status sws_pool2d(sws_op op, const float *x, float *y, int64_t N, int64_t C,
                       int64_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
                       int32_t ph, int32_t pw, float scale, void *stream);
 
+/* sws_pool2d on 16-bit storage, defined like sws_slide1d_16: x and y hold bf16 or fp16 elements,
+ * each widened to fp32 exactly; the window is combined in fp32 as in sws_pool2d, multiplied by
+ * scale (ADD) and rounded to the storage type once, to nearest even.  MAX / MIN are exact.
+ *   x : device, N*C*H*W 16-bit elements     y : device, N*C*Ho*Wo 16-bit elements
+ * Errors: as sws_pool2d, and INVALID_ARG for an unknown dtype. */
+sws_status sws_pool2d_16(sws_op op, sws_dtype dtype, const void *x, void *y, int64_t N, int64_t C,
+                         int64_t H, int64_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                         int32_t ph, int32_t pw, float scale, void *stream);
+
 /* What an ADD result of sws_pool2d_ex is divided by. */
 typedef enum {
     SWS_DIV_SCALE = 0,         /* nothing: y = scale * sum (scale = 1/(kh*kw): the average that counts padding) */

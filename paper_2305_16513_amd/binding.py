@@ -19,7 +19,7 @@ _lib = None
 
 _i64, _i32, _f32, _vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
 
-EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_pool2d_ex", "sws_conv1d", "sws_conv1d_grad_input", "sws_conv1d_grad_weight", "sws_conv2d", "sws_conv2d_grad_input", "sws_conv2d_grad_weight", "sws_copy", "sws_out_len",
+EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_pool2d_16", "sws_pool2d_ex", "sws_conv1d", "sws_conv1d_grad_input", "sws_conv1d_grad_weight", "sws_conv2d", "sws_conv2d_grad_input", "sws_conv2d_grad_weight", "sws_copy", "sws_out_len",
            "sws_status_string", "sws_set_option", "sws_version")
 
 
@@ -48,6 +48,9 @@ def lib():
         L.sws_pool2d.restype = ctypes.c_int
         L.sws_pool2d.argtypes = [ctypes.c_int, _vp, _vp, _i64, _i64, _i64, _i64,
                                  _i32, _i32, _i32, _i32, _i32, _i32, _f32, _vp]
+        L.sws_pool2d_16.restype = ctypes.c_int
+        L.sws_pool2d_16.argtypes = [ctypes.c_int, ctypes.c_int, _vp, _vp, _i64, _i64, _i64, _i64,
+                                    _i32, _i32, _i32, _i32, _i32, _i32, _f32, _vp]
         L.sws_pool2d_ex.restype = ctypes.c_int
         L.sws_pool2d_ex.argtypes = [ctypes.c_int, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32,
                                     _i32, _i32, _i32, _i32, ctypes.c_int, _f32, _vp]
@@ -206,6 +209,27 @@ def sws_pool2d(op, x, kh, kw, sh=1, sw=1, ph=0, pw=0, scale=1.0, y=None, stream=
     y = _out(y, (n, c, ho, wo), x)
     _check(lib().sws_pool2d(op, x.data_ptr(), y.data_ptr(), n, c, h, wd, kh, kw, sh, sw, ph, pw, scale,
                             _stream(stream)), "sws_pool2d")
+    return y
+
+
+def sws_pool2d_16(op, x, kh, kw, sh=1, sw=1, ph=0, pw=0, scale=1.0, y=None, stream=None):
+    """x [N, C, H, W] of bfloat16 or float16 -> y [N, C, Ho, Wo] of the same type (fp32 arithmetic)."""
+    if not isinstance(x, torch.Tensor) or not x.is_cuda:
+        raise TypeError("x must be a GPU tensor")
+    if x.dtype not in _DTYPE_16 or not x.is_contiguous():
+        raise TypeError("x must be contiguous bfloat16 or float16")
+    n, c, h, wd = x.shape
+    ho, wo = sws_out_len(h, kh, sh, ph), sws_out_len(wd, kw, sw, pw)
+    if ho < 1 or wo < 1:
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_pool2d_16")
+    shape = (n, c, ho, wo)
+    if y is None:
+        y = torch.empty(shape, dtype=x.dtype, device=x.device)
+    elif (not isinstance(y, torch.Tensor) or not y.is_cuda or y.dtype != x.dtype or not y.is_contiguous()
+          or tuple(y.shape) != shape):
+        raise TypeError("y must be a contiguous GPU tensor of x's type and shape %s" % (shape,))
+    _check(lib().sws_pool2d_16(op, _DTYPE_16[x.dtype], x.data_ptr(), y.data_ptr(), n, c, h, wd, kh, kw, sh, sw, ph, pw,
+                               scale, _stream(stream)), "sws_pool2d_16")
     return y
 
 

@@ -27,17 +27,49 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Element types in memory: fp32, or bf16 / fp16 widened exactly on the way in and rounded to nearest
+// even once on the way out (all arithmetic is fp32).
+template <typename T> struct Io;
+template <> struct Io<float> {
+    static __device__ __forceinline__ v4f load4(const float *p) { return *(const v4f_u *)p; }
+    static __device__ __forceinline__ float load1(const float *p) { return *p; }
+    static __device__ __forceinline__ void store1(float *p, float v) { *p = v; }
+    static __device__ __forceinline__ void store1_nt(float *p, float v) { __builtin_nontemporal_store(v, p); }
+    static __device__ __forceinline__ void store4(float *p, v4f o, bool plain)
+    {
+        if (plain) *(v4f_u *)p = o;
+        else __builtin_nontemporal_store(o, (v4f_u *)p);
+    }
+};
+template <typename T> struct Io16 {
+    typedef T v4 __attribute__((ext_vector_type(4)));
+    typedef v4 v4_u __attribute__((aligned(2)));
+    static __device__ __forceinline__ v4f load4(const T *p) { return __builtin_convertvector(*(const v4_u *)p, v4f); }
+    static __device__ __forceinline__ float load1(const T *p) { return (float)*p; }
+    static __device__ __forceinline__ void store1(T *p, float v) { *p = (T)v; }
+    static __device__ __forceinline__ void store1_nt(T *p, float v) { *p = (T)v; }
+    static __device__ __forceinline__ void store4(T *p, v4f o, bool plain)
+    {
+        const v4 h = __builtin_convertvector(o, v4);
+        if (plain) *(v4_u *)p = h;
+        else __builtin_nontemporal_store(h, (v4_u *)p);
+    }
+};
+template <> struct Io<__bf16> : Io16<__bf16> {};
+template <> struct Io<_Float16> : Io16<_Float16> {};
+
 // R = consecutive output rows per lane: 4 at stride 1 (each staged row feeds up to KH of them);
 // 1 at larger strides, where rows overlap little and consecutive lanes then store one
 // contiguous run of y.
 template <int SH> struct RowsPerItem { static constexpr int value = (SH == 1) ? 4 : 1; };
 
-template <int OP, int KH, int KW, int SH, int SW, int PW>
+template <int OP, int KH, int KW, int SH, int SW, int PW, typename T>
 __global__ __launch_bounds__(kThreads) void pool2d_band_kernel(
-    const float *__restrict__ x, float *__restrict__ y, int H, int W, int Ho, int Wo, int ph, int P, int TH,
+    const T *__restrict__ x, T *__restrict__ y, int H, int W, int Ho, int Wo, int ph, int P, int TH,
     int bands, float scale, int64_t n_units, int lds_floats, int flags)
 {
     using O = Op<OP>;
+    using IO = Io<T>;
     constexpr int R = RowsPerItem<SH>::value;
     constexpr int NR = (R - 1) * SH + KH;            // input rows per item
     constexpr int LPAD = (PW + 3) / 4 * 4;           // aligned columns read left of the window
@@ -56,8 +88,8 @@ __global__ __launch_bounds__(kThreads) void pool2d_band_kernel(
     float *lds = lds_all + wave * lds_floats;
     const int64_t plane = unit / bands;
     const int band = (int)(unit - plane * bands);
-    const float *xp = x + plane * (int64_t)H * W;
-    float *yp = y + plane * (int64_t)Ho * Wo;
+    const T *xp = x + plane * (int64_t)H * W;
+    T *yp = y + plane * (int64_t)Ho * Wo;
     const int ho0 = band * TH;                       // first output row of the band
     int ho1 = ho0 + TH;
     if (ho1 > Ho) ho1 = Ho;
@@ -70,14 +102,14 @@ __global__ __launch_bounds__(kThreads) void pool2d_band_kernel(
     if (P == W) {
         // the band is one contiguous range: all its 128-bit loads are issued before the first
         // LDS write (lanes past the end re-read element 0 and drop it)
-        const float *src = xp + (int64_t)row_lo * W;
+        const T *src = xp + (int64_t)row_lo * W;
         const int n = (row_hi - row_lo) * W;         // multiple of 4, at most kLdsBudget / 4
         constexpr int NL = kLdsBudget / 16 / kWave;
         v4f g[NL];
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
             const int i = 4 * (lane + kWave * j);
-            g[j] = *(const v4f_u *)(src + (i < n ? i : 0));
+            g[j] = IO::load4(src + (i < n ? i : 0));
         }
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
@@ -88,7 +120,7 @@ __global__ __launch_bounds__(kThreads) void pool2d_band_kernel(
         const int n = (row_hi - row_lo) * P;
         for (int i = lane; i < n; i += kWave) {
             const int r = i / P, c = i - r * P;
-            lds[i] = (c < W) ? xp[(int64_t)(row_lo + r) * W + c] : O::id();
+            lds[i] = (c < W) ? IO::load1(xp + (int64_t)(row_lo + r) * W + c) : O::id();
         }
     }
     wave_lds_sync();
@@ -145,14 +177,18 @@ __global__ __launch_bounds__(kThreads) void pool2d_band_kernel(
                 }
                 o[e] = acc;
             }
-            float *dst = yp + (int64_t)(ho + ro) * Wo + 4 * cg;
+            T *dst = yp + (int64_t)(ho + ro) * Wo + 4 * cg;
             if (4 * cg + 4 <= Wo) {
-                if (flags & 4) *(v4f_u *)dst = (v4f){o[0], o[1], o[2], o[3]};
-                else __builtin_nontemporal_store((v4f){o[0], o[1], o[2], o[3]}, (v4f_u *)dst);
+                if constexpr (sizeof(T) == 4) {
+                    if (flags & 4) *(v4f_u *)dst = (v4f){o[0], o[1], o[2], o[3]};
+                    else __builtin_nontemporal_store((v4f){o[0], o[1], o[2], o[3]}, (v4f_u *)dst);
+                } else {
+                    IO::store4(dst, (v4f){o[0], o[1], o[2], o[3]}, (flags & 4) != 0);
+                }
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    if (4 * cg + e < Wo) dst[e] = o[e];
+                    if (4 * cg + e < Wo) IO::store1(dst + e, o[e]);
             }
         }
     }
@@ -184,8 +220,8 @@ BandPlan plan_bands(int W, int Ho, int Wo, int KH, int SH, int R)
     return p;
 }
 
-template <int OP, int KH, int KW, int SH, int SW, int PW>
-hipError_t launch_band(const float *x, float *y, int64_t planes, int H, int W, int Ho, int Wo, int ph, float scale,
+template <int OP, int KH, int KW, int SH, int SW, int PW, typename T>
+hipError_t launch_band(const T *x, T *y, int64_t planes, int H, int W, int Ho, int Wo, int ph, float scale,
                        int div_valid, hipStream_t s, bool *taken)
 {
     const BandPlan p = plan_bands(W, Ho, Wo, KH, SH, RowsPerItem<SH>::value);
@@ -196,7 +232,7 @@ hipError_t launch_band(const float *x, float *y, int64_t planes, int H, int W, i
     const int64_t n_wg = (n_units + kWaves - 1) / kWaves;
     const int64_t grid = (flags & 2) ? xcd_grid(n_wg) : n_wg;
     if (grid > 2147483647LL) { *taken = false; return hipSuccess; }
-    hipLaunchKernelGGL((pool2d_band_kernel<OP, KH, KW, SH, SW, PW>), dim3((unsigned)grid), dim3(kThreads),
+    hipLaunchKernelGGL((pool2d_band_kernel<OP, KH, KW, SH, SW, PW, T>), dim3((unsigned)grid), dim3(kThreads),
                        p.lds_bytes * kWaves, s, x, y, H, W, Ho, Wo, ph, p.P, p.TH, p.bands, scale, n_units,
                        (int)(p.lds_bytes / 4), flags);
     return hipGetLastError();
@@ -211,14 +247,15 @@ hipError_t launch_band(const float *x, float *y, int64_t planes, int H, int W, i
 // ------------------------------------------------------------------------------------------------
 constexpr int kSepLds = 12 * 1024;                   // bytes of LDS per wavefront
 
-template <int OP>
-__global__ __launch_bounds__(kThreads) void pool2d_sep_kernel(const float *__restrict__ x, float *__restrict__ y, int H,
+template <int OP, typename T>
+__global__ __launch_bounds__(kThreads) void pool2d_sep_kernel(const T *__restrict__ x, T *__restrict__ y, int H,
                                                               int W, int Ho, int Wo, int kh, int kw, int sh, int sw,
                                                               int ph, int pw, int P, int PC, int pwl, int TH, int bands,
                                                               float scale, int64_t n_units, int lds_floats,
                                                               int in_rows, int div_valid)
 {
     using O = Op<OP>;
+    using IO = Io<T>;
     extern __shared__ __attribute__((aligned(16))) float lds_all[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
@@ -231,8 +268,8 @@ __global__ __launch_bounds__(kThreads) void pool2d_sep_kernel(const float *__res
     float *col = in + in_rows * P;
     const int64_t plane = unit / bands;
     const int band = (int)(unit - plane * bands);
-    const float *xp = x + plane * (int64_t)H * W;
-    float *yp = y + plane * (int64_t)Ho * Wo;
+    const T *xp = x + plane * (int64_t)H * W;
+    T *yp = y + plane * (int64_t)Ho * Wo;
     const int ho0 = band * TH;
     int ho1 = ho0 + TH;
     if (ho1 > Ho) ho1 = Ho;
@@ -250,14 +287,14 @@ __global__ __launch_bounds__(kThreads) void pool2d_sep_kernel(const float *__res
     if (P == W) {
         // the real rows are one contiguous range: all its 128-bit loads are issued before the first
         // LDS write (lanes past the end re-read element 0 and drop it)
-        const float *src = xp + (int64_t)row_lo * W;
+        const T *src = xp + (int64_t)row_lo * W;
         const int n4 = (row_hi - row_lo) * P4;
         constexpr int NL = kSepLds / 16 / kWave;
         v4f g4[NL];
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
             const int i = lane + kWave * j;
-            g4[j] = *(const v4f_u *)(src + (i < n4 ? 4 * i : 0));
+            g4[j] = IO::load4(src + (i < n4 ? 4 * i : 0));
         }
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
@@ -269,7 +306,7 @@ __global__ __launch_bounds__(kThreads) void pool2d_sep_kernel(const float *__res
         const float inv_p = 1.0f / (float)P;
         for (int i = lane; i < n; i += kWave) {
             const int r = (int)(((float)i + 0.5f) * inv_p), c = i - r * P;
-            in_real[i] = (c < W) ? xp[(int64_t)(row_lo + r) * W + c] : O::id();
+            in_real[i] = (c < W) ? IO::load1(xp + (int64_t)(row_lo + r) * W + c) : O::id();
         }
     }
     // identity margins of col: pwl columns in front, PC - pwl - P behind
@@ -323,12 +360,12 @@ __global__ __launch_bounds__(kThreads) void pool2d_sep_kernel(const float *__res
             }
             acc *= sc;
         }
-        __builtin_nontemporal_store(acc, yp + (int64_t)ho * Wo + wo);
+        IO::store1_nt(yp + (int64_t)ho * Wo + wo, acc);
     }
 }
 
-template <int OP>
-hipError_t launch_sep(const float *x, float *y, int64_t planes, int H, int W, int Ho, int Wo, int kh, int kw, int sh,
+template <int OP, typename T>
+hipError_t launch_sep(const T *x, T *y, int64_t planes, int H, int W, int Ho, int Wo, int kh, int kw, int sh,
                       int sw, int ph, int pw, float scale, int div_valid, hipStream_t s, bool *taken)
 {
     const int P = (W + 3) / 4 * 4;
@@ -349,19 +386,19 @@ hipError_t launch_sep(const float *x, float *y, int64_t planes, int H, int W, in
     const int64_t n_units = planes * bands;
     const int64_t grid = (n_units + kWaves - 1) / kWaves;
     if (grid > 2147483647LL) { *taken = false; return hipSuccess; }
-    hipLaunchKernelGGL((pool2d_sep_kernel<OP>), dim3((unsigned)grid), dim3(kThreads), (size_t)lds_floats * 4 * kWaves, s,
+    hipLaunchKernelGGL((pool2d_sep_kernel<OP, T>), dim3((unsigned)grid), dim3(kThreads), (size_t)lds_floats * 4 * kWaves, s,
                        x, y, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, P, PC, pwl, TH, bands, scale, n_units, lds_floats,
                        in_rows, div_valid);
     return hipGetLastError();
 }
 
-template <int OP>
-hipError_t dispatch_band(const float *x, float *y, int64_t planes, int H, int W, int Ho, int Wo, int kh, int kw,
+template <int OP, typename T>
+hipError_t dispatch_band(const T *x, T *y, int64_t planes, int H, int W, int Ho, int Wo, int kh, int kw,
                          int sh, int sw, int ph, int pw, float scale, int div_valid, hipStream_t s, bool *taken)
 {
 #define SWS_BAND(KH, KW, SH, SW, PW)                                                                  \
     if (kh == KH && kw == KW && sh == SH && sw == SW && pw == PW)                                      \
-        return launch_band<OP, KH, KW, SH, SW, PW>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken)
+        return launch_band<OP, KH, KW, SH, SW, PW, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken)
     SWS_BAND(3, 3, 1, 1, 1);
     SWS_BAND(3, 3, 2, 2, 1);
     SWS_BAND(3, 3, 1, 1, 0);
@@ -378,6 +415,77 @@ hipError_t dispatch_band(const float *x, float *y, int64_t planes, int H, int W,
     return hipSuccess;
 }
 
+// The tuned kernels for one element type: a specialised band kernel if the geometry has one, else
+// the run-time separable kernel.  *taken = false: neither covers the shape, nothing was launched.
+template <typename T>
+hipError_t pool2d_tuned(int op, const T *x, T *y, int64_t planes, int H, int W, int Ho, int Wo, int kh, int kw, int sh,
+                        int sw, int ph, int pw, float scale, int div_valid, hipStream_t s, bool *taken)
+{
+    hipError_t e;
+    switch (op) {
+    case SWS_OP_ADD: e = dispatch_band<SWS_OP_ADD, T>(x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, div_valid, s, taken); break;
+    case SWS_OP_MAX: e = dispatch_band<SWS_OP_MAX, T>(x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, div_valid, s, taken); break;
+    default: e = dispatch_band<SWS_OP_MIN, T>(x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, div_valid, s, taken); break;
+    }
+    if (*taken) return e;
+    switch (op) {
+    case SWS_OP_ADD: return launch_sep<SWS_OP_ADD, T>(x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, div_valid, s, taken);
+    case SWS_OP_MAX: return launch_sep<SWS_OP_MAX, T>(x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, div_valid, s, taken);
+    default: return launch_sep<SWS_OP_MIN, T>(x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, div_valid, s, taken);
+    }
+}
+
+// Direct evaluation on 16-bit elements (planes too wide for the LDS slices): one thread per output.
+template <int OP, typename T>
+__global__ __launch_bounds__(kThreads) void pool2d16_naive_kernel(const T *__restrict__ x, T *__restrict__ y,
+                                                                  int64_t planes, int H, int W, int Ho, int Wo, int kh,
+                                                                  int kw, int sh, int sw, int ph, int pw, float scale)
+{
+    using O = Op<OP>;
+    const int64_t total = planes * (int64_t)Ho * Wo;
+    for (int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x; o < total; o += (int64_t)gridDim.x * kThreads) {
+        const int wo = (int)(o % Wo);
+        const int ho = (int)((o / Wo) % Ho);
+        const T *xp = x + (o / ((int64_t)Wo * Ho)) * (int64_t)H * W;
+        float acc = O::id();
+        for (int b = 0; b < kw; ++b) {
+            const int c = wo * sw - pw + b;
+            if (c < 0 || c >= W) continue;
+            float colv = O::id();
+            for (int a = 0; a < kh; ++a) {
+                const int h = ho * sh - ph + a;
+                if (h >= 0 && h < H) colv = O::f(colv, (float)xp[(int64_t)h * W + c]);
+            }
+            acc = O::f(acc, colv);
+        }
+        if (OP == SWS_OP_ADD) acc *= scale;
+        y[o] = (T)acc;
+    }
+}
+
+template <typename T>
+hipError_t pool2d_16(int op, const T *x, T *y, int64_t planes, int H, int W, int Ho, int Wo, int kh, int kw, int sh,
+                     int sw, int ph, int pw, float scale, hipStream_t s)
+{
+    if (g_opt.pool2d_variant != 1) {
+        bool taken = false;
+        const hipError_t e = pool2d_tuned<T>(op, x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, 0, s, &taken);
+        if (taken) return e;
+    }
+    int64_t grid = (planes * (int64_t)Ho * Wo + kThreads - 1) / kThreads;
+    if (grid > 1048576) grid = 1048576;
+#define SWS_P16(OPV)                                                                                            \
+    hipLaunchKernelGGL((pool2d16_naive_kernel<OPV, T>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, planes, H, W, \
+                       Ho, Wo, kh, kw, sh, sw, ph, pw, scale)
+    switch (op) {
+    case SWS_OP_ADD: SWS_P16(SWS_OP_ADD); break;
+    case SWS_OP_MAX: SWS_P16(SWS_OP_MAX); break;
+    default: SWS_P16(SWS_OP_MIN); break;
+    }
+#undef SWS_P16
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_pool2d(int op, const float *x, float *y, int64_t planes, int64_t H, int64_t W, int64_t Ho,
@@ -388,40 +496,23 @@ hipError_t launch_pool2d(int op, const float *x, float *y, int64_t planes, int64
     // beyond the plane hold the identity whichever side they are on).
     if (g_opt.pool2d_variant != 1) {
         bool taken = false;
-        hipError_t e;
-        switch (op) {
-        case SWS_OP_ADD:
-            e = dispatch_band<SWS_OP_ADD>(x, y, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw,
-                                          scale, div_valid, s, &taken);
-            break;
-        case SWS_OP_MAX:
-            e = dispatch_band<SWS_OP_MAX>(x, y, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw,
-                                          scale, div_valid, s, &taken);
-            break;
-        default:
-            e = dispatch_band<SWS_OP_MIN>(x, y, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw,
-                                          scale, div_valid, s, &taken);
-            break;
-        }
-        if (taken) return e;
-        // no specialised kernel for this geometry: the run-time separable kernel
-        switch (op) {
-        case SWS_OP_ADD:
-            e = launch_sep<SWS_OP_ADD>(x, y, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw, scale,
-                                       div_valid, s, &taken);
-            break;
-        case SWS_OP_MAX:
-            e = launch_sep<SWS_OP_MAX>(x, y, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw, scale,
-                                       div_valid, s, &taken);
-            break;
-        default:
-            e = launch_sep<SWS_OP_MIN>(x, y, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw, scale,
-                                       div_valid, s, &taken);
-            break;
-        }
+        const hipError_t e = pool2d_tuned<float>(op, x, y, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw,
+                                                 scale, div_valid, s, &taken);
         if (taken) return e;
     }
     return launch_pool2d_naive(op, x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, div_valid, s);
+}
+
+// 16-bit storage (dtype SWS_DTYPE_BF16 / SWS_DTYPE_F16), fp32 arithmetic, one rounding per output.
+hipError_t launch_pool2d_16(int op, int dtype, const void *x, void *y, int64_t planes, int64_t H, int64_t W, int64_t Ho,
+                            int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
+                            float scale, hipStream_t s)
+{
+    if (dtype == SWS_DTYPE_BF16)
+        return pool2d_16<__bf16>(op, (const __bf16 *)x, (__bf16 *)y, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh,
+                                 sw, ph, pw, scale, s);
+    return pool2d_16<_Float16>(op, (const _Float16 *)x, (_Float16 *)y, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw,
+                               sh, sw, ph, pw, scale, s);
 }
 
 }  // namespace sws

@@ -102,3 +102,42 @@ def test_argument_checks(B):
         B.sws_slide1d_16(0, x.float(), 3)
     assert B.lib().sws_slide1d_16(0, 7, x.data_ptr(), x.data_ptr(), 2, 100, 3, 1.0, None) == B.SWS_ERR_INVALID_ARG
     assert B.lib().sws_slide1d_16(5, 1, x.data_ptr(), x.data_ptr(), 2, 100, 3, 1.0, None) == B.SWS_ERR_INVALID_ARG
+
+
+# ------------------------------------------------------------------------------ 2-D pooling on 16-bit storage
+POOL_GEOMS = [(3, 3, 1, 1, 1, 1), (3, 3, 2, 2, 1, 1), (2, 2, 2, 2, 0, 0), (5, 5, 1, 1, 2, 2), (7, 7, 1, 1, 3, 3),
+              (4, 4, 4, 4, 0, 0), (11, 11, 1, 1, 5, 5), (1, 7, 1, 1, 0, 3), (6, 3, 2, 1, 2, 1)]
+
+
+@pytest.mark.parametrize("kind", ["bf16", "f16"])
+@pytest.mark.parametrize("op", ["add", "max", "min"])
+@pytest.mark.parametrize("geom", POOL_GEOMS)
+@pytest.mark.parametrize("shape", [(2, 3, 37, 53), (1, 4, 112, 112), (2, 2, 9, 3000)])
+def test_pool2d_16(B, kind, op, geom, shape):
+    """sws_pool2d_16 against round16(pool2d(x widened)): specialised band kernels, the run-time
+    separable kernel, and (the 3000-wide planes) direct evaluation."""
+    kh, kw, sh, sw, ph, pw = geom
+    tdt, odt, half_step = TYPES[kind]
+    rng = np.random.Generator(np.random.PCG64(kh * 97 + kw * 13 + shape[3]))
+    xq = torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)).to(tdt)
+    scale = 1.0 / (kh * kw)
+    y = B.sws_pool2d_16(OPS[op], xq.cuda(), kh, kw, sh, sw, ph, pw, scale)
+    assert y.dtype == tdt
+    got = y.cpu().to(torch.float64).numpy()
+    ref, mag = oracle.pool2d(OPS[op], xq.to(torch.float32).numpy(), kh, kw, sh, sw, ph, pw, scale)
+    what = "%s %s %s %s" % (kind, op, geom, shape)
+    if op != "add":
+        assert np.array_equal(got, ref), what
+        return
+    allowed = TOL * mag + (np.abs(ref) + TOL * mag) * half_step + (2.0 ** -25 if kind == "f16" else 0.0)
+    assert (np.abs(got - ref) <= allowed).all(), what
+    # (sums of normal data cancel: the fp32 error is a larger share of a 16-bit step than for the sliding sums above)
+    assert (got == oracle.round16(ref, odt)).mean() > 0.97, what
+
+
+def test_pool2d_16_argument_checks(B):
+    x = torch.zeros((1, 2, 8, 8), dtype=torch.float16, device="cuda")
+    with pytest.raises(TypeError):
+        B.sws_pool2d_16(0, x.float(), 3, 3)
+    assert B.lib().sws_pool2d_16(0, 0, x.data_ptr(), x.data_ptr(), 1, 2, 8, 8, 3, 3, 1, 1, 1, 1, 1.0, None) == B.SWS_ERR_INVALID_ARG
+    assert B.lib().sws_pool2d_16(0, 2, x.data_ptr(), x.data_ptr(), 1, 2, 8, 8, 3, 3, 1, 1, 3, 1, 1.0, None) == B.SWS_ERR_INVALID_ARG
