@@ -59,6 +59,8 @@ def _load():
         for f in (lib.sws_ref_conv2d_grad_input, lib.sws_ref_conv2d_grad_weight):
             f.restype = ctypes.c_int
             f.argtypes = [_fp, _fp, _dp, _dp, _i64, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _i32]
+        lib.sws_ref_maxpool2d_grad.restype = ctypes.c_int
+        lib.sws_ref_maxpool2d_grad.argtypes = [_fp, _fp, _dp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _i32]
         lib.sws_ref_round16.restype = ctypes.c_int
         lib.sws_ref_round16.argtypes = [_dp, _dp, _i64, ctypes.c_int]
         lib.sws_ref_conv1d.restype = ctypes.c_int
@@ -307,3 +309,19 @@ def conv2d_grad_weight(x, gy, kh, kw, sh=1, sw=1, ph=0, pw=0):
     if rc:
         raise ValueError("sws_ref_conv2d_grad_weight rejected its arguments")
     return gw, s
+
+
+def maxpool2d_grad(x, gy, kh, kw, sh=1, sw=1, ph=0, pw=0):
+    """x: [N, C, H, W], gy: [N, C, Ho, Wo] float32 -> gx [N, C, H, W] float64: every window's gradient
+    goes to the first cell (row-major) holding its maximum."""
+    x = _f32(x)
+    gy = _f32(gy)
+    n, c, h, wd = x.shape
+    ho, wo = (h + 2 * ph - kh) // sh + 1, (wd + 2 * pw - kw) // sw + 1
+    if tuple(gy.shape) != (n, c, ho, wo):
+        raise ValueError("gy does not have the pooled shape")
+    gx = np.empty((n, c, h, wd), np.float64)
+    rc = _load().sws_ref_maxpool2d_grad(_ptr_f(x), _ptr_f(gy), _ptr_d(gx), n, c, h, wd, kh, kw, sh, sw, ph, pw)
+    if rc:
+        raise ValueError("sws_ref_maxpool2d_grad rejected its arguments")
+    return gx

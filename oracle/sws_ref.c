@@ -22,6 +22,9 @@
  *   sws_ref_pool2d_ex  the same window scan with separate padding on the four sides and, for
  *                    ADD, the choice of dividing by the number of window cells that lie inside
  *                    the plane (average pooling that does not count the padding).
+ *   sws_ref_maxpool2d_grad  the adjoint of max pooling at a point x (Section 2.3's max operator,
+ *                    training side): every window sends its output gradient to the cell that
+ *                    holds its maximum — the first such cell in row-major order when several tie.
  *   sws_ref_slide1d_padded  Eq. 3 on rows extended at both ends (the boundary conditions
  *                    named in Section 3: padding, mirroring, periodicity; plus edge
  *                    replication).  Every window element's index is mapped back into
@@ -531,4 +534,39 @@ int sws_ref_conv2d_grad_weight(const float *x, const float *gy, double *gw, doub
                                int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw)
 {
     return conv2d_adjoint(1, x, gy, gw, abs_sum, N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw);
+}
+
+/* Gradient of loss = sum(gy * maxpool(x)) with respect to x (sws_ref_pool2d with op = max, same
+ * geometry).  Scatter form: for every window, scan its cells inside the plane in row-major order,
+ * keep the first cell whose value is strictly greater than all before it, add gy there.
+ * gx: N*C*H*W doubles, overwritten. */
+int sws_ref_maxpool2d_grad(const float *x, const float *gy, double *gx, int64_t N, int64_t C, int64_t H, int64_t W,
+                           int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw)
+{
+    if (N < 0 || C < 0 || H < 0 || W < 0) return 1;
+    if (kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0) return 1;
+    if (ph >= kh || pw >= kw) return 1;
+    if (kh > H + 2 * (int64_t)ph || kw > W + 2 * (int64_t)pw) return 1;
+    const int64_t Ho = (H + 2 * (int64_t)ph - kh) / sh + 1;
+    const int64_t Wo = (W + 2 * (int64_t)pw - kw) / sw + 1;
+    const int64_t planes = N * C;
+    if (planes > 0 && (!x || !gy || !gx)) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t p = 0; p < planes; ++p) {
+        const float *xp = x + p * H * W;
+        double *gp = gx + p * H * W;
+        for (int64_t e = 0; e < H * W; ++e) gp[e] = 0.0;
+        for (int64_t ho = 0; ho < Ho; ++ho)
+            for (int64_t wo = 0; wo < Wo; ++wo) {
+                int64_t best = -1;
+                for (int32_t a = 0; a < kh; ++a)
+                    for (int32_t b = 0; b < kw; ++b) {
+                        const int64_t h = ho * sh - ph + a, c = wo * sw - pw + b;
+                        if (h < 0 || h >= H || c < 0 || c >= W) continue;
+                        if (best < 0 || xp[h * W + c] > xp[best]) best = h * W + c;
+                    }
+                gp[best] += (double)gy[(p * Ho + ho) * Wo + wo];
+            }
+    }
+    return 0;
 }

@@ -913,3 +913,38 @@ def test_conv2d_adjoints_on_one_row_planes_are_the_1d_adjoints_and_a_hand_case()
     assert gx[0, 0].tolist() == [[0, 0, 0], [20, 40, 0], [60, 80, 0]]
     gw, _ = oracle.conv2d_grad_weight(xh, gh, 2, 2)
     assert gw[0, 0].tolist() == [[8, 10], [14, 16]]
+
+
+# ----------------------------------------------------------------------------- P16
+# The adjoint of max pooling: gradients routed to the (first) maximum of every window.
+def test_maxpool2d_grad_hand_written_case_and_tie_rule():
+    x = np.array([[[[1, 5, 2], [7, 3, 7], [0, 4, 6]]]], np.float32)
+    gy = np.array([[[[1, 10], [100, 1000]]]], np.float32)                  # 2 x 2 windows, stride 1
+    gx = oracle.maxpool2d_grad(x, gy, 2, 2)
+    # windows: [[1,5],[7,3]] -> 7 at (1,0); [[5,2],[3,7]] -> 7 at (1,2); [[7,3],[0,4]] -> 7 at (1,0); [[3,7],[4,6]] -> 7 at (1,2)
+    assert gx[0, 0].tolist() == [[0, 0, 0], [101, 0, 1010], [0, 0, 0]]
+    flat = np.full((1, 1, 3, 3), 2.0, np.float32)                          # all equal: the first cell of each window
+    gx = oracle.maxpool2d_grad(flat, gy, 2, 2)
+    assert gx[0, 0].tolist() == [[1, 10, 0], [100, 1000, 0], [0, 0, 0]]
+    gx = oracle.maxpool2d_grad(flat, np.ones((1, 1, 3, 3), np.float32), 3, 3, 1, 1, 1, 1)     # padded: first cell inside the plane
+    assert gx[0, 0].tolist() == [[4, 2, 0], [2, 1, 0], [0, 0, 0]]
+
+
+@pytest.mark.parametrize("geom", [(3, 3, 1, 1, 1, 1), (3, 3, 2, 2, 1, 1), (2, 2, 2, 2, 0, 0), (4, 2, 3, 1, 2, 0), (1, 5, 1, 2, 0, 4)])
+def test_maxpool2d_grad_is_the_derivative_of_the_pooled_loss(geom):
+    """On distinct values max pooling is linear near x: central differences of sum(gy * maxpool(x)) with a step
+    that keeps the order are its exact partial derivatives; and gradients are conserved."""
+    kh, kw, sh, sw, ph, pw = geom
+    r = _rng(230 + kh * 7 + kw)
+    x = r.permutation(2 * 3 * 9 * 11).reshape(2, 3, 9, 11).astype(np.float32)      # distinct integers
+    y, _ = oracle.pool2d(oracle.OP_MAX, x, kh, kw, sh, sw, ph, pw)
+    gy = r.integers(-3, 4, y.shape).astype(np.float32)
+    gx = oracle.maxpool2d_grad(x, gy, kh, kw, sh, sw, ph, pw)
+    loss = lambda xx: float((oracle.pool2d(oracle.OP_MAX, xx, kh, kw, sh, sw, ph, pw)[0] * gy).sum())
+    for idx in list(np.ndindex(x.shape))[::5]:
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += 0.25
+        xm[idx] -= 0.25
+        assert (loss(xp) - loss(xm)) / 0.5 == gx[idx]
+    assert gx.sum() == float(gy.astype(np.float64).sum())
+    assert np.array_equal(gx.sum(axis=(2, 3)), gy.astype(np.float64).sum(axis=(2, 3)))
