@@ -130,6 +130,19 @@ sws_status sws_pool2d(sws_op op, const float *x, float *y, int64_t N, int64_t C,
                       int64_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
                       int32_t ph, int32_t pw, float scale, void *stream);
 
+/* The adjoint of max pooling (sws_pool2d with SWS_OP_MAX, same geometry) at the point x: with
+ * loss = sum(gy * y), every window adds its gy to the gx of the cell that holds its maximum — the
+ * first such cell in row-major order of the window when several tie (padding never wins).
+ *   x, gx : device, N*C*H*W floats     gy : device, N*C*Ho*Wo floats
+ * gx is overwritten (cells no window chose get 0).  Deterministic: a cell adds the gradients of
+ * the windows that chose it in a fixed order, without atomic operations.
+ * Average pooling needs no entry point of its own: its adjoint is a sliding add of gy
+ * (sws_slide1d_padded / sws_pool2d_ex with identity padding k - 1 - pad).
+ * Errors: as sws_pool2d. */
+sws_status sws_maxpool2d_grad(const float *x, const float *gy, float *gx, int64_t N, int64_t C,
+                              int64_t H, int64_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                              int32_t ph, int32_t pw, void *stream);
+
 /* sws_pool2d on 16-bit storage, defined like sws_slide1d_16: x and y hold bf16 or fp16 elements,
  * each widened to fp32 exactly; the window is combined in fp32 as in sws_pool2d, multiplied by
  * scale (ADD) and rounded to the storage type once, to nearest even.  MAX / MIN are exact.

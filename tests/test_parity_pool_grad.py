@@ -1,0 +1,88 @@
+"""GPU parity of sws_maxpool2d_grad (gradients routed to the first maximum of every window) against
+the CPU oracle: |err| <= 1e-5 * sum|routed gradients| per cell; bit-exact on integer gradients."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2305_16513_amd import workloads
+from parity_util import assert_within_tol, to_gpu, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2305_16513_amd import binding
+    binding.lib()
+    yield binding
+    binding.sws_set_option("pool2d_variant", 0)
+
+
+GEOMS = [(3, 3, 1, 1, 1, 1), (3, 3, 2, 2, 1, 1), (2, 2, 2, 2, 0, 0), (3, 3, 1, 1, 0, 0), (5, 5, 1, 1, 2, 2), (4, 2, 3, 1, 2, 0),
+         (1, 7, 1, 2, 0, 3), (7, 1, 2, 1, 3, 0), (2, 2, 3, 3, 0, 0), (3, 3, 3, 3, 1, 1), (11, 11, 1, 1, 5, 5), (1, 1, 1, 1, 0, 0)]
+
+
+def _check(B, x, gy, geom, what):
+    gx = to_host(B.sws_maxpool2d_grad(to_gpu(x), to_gpu(gy), *geom))
+    ref = oracle.maxpool2d_grad(x, gy, *geom)
+    mag = oracle.maxpool2d_grad(x, np.abs(gy), *geom)
+    assert_within_tol(gx, ref, mag, what)
+    return gx, ref
+
+
+@pytest.mark.parametrize("geom", GEOMS)
+@pytest.mark.parametrize("shape", [(2, 3, 37, 53), (1, 2, 112, 112), (3, 1, 16, 200), (1, 2, 129, 19), (1, 1, 1, 1), (2, 2, 5, 4000)])
+def test_geometries(B, geom, shape):
+    kh, kw, sh, sw, ph, pw = geom
+    if kh > shape[2] + 2 * ph or kw > shape[3] + 2 * pw:
+        pytest.skip("window larger than plane")
+    r = np.random.Generator(np.random.PCG64(kh * 100 + kw * 10 + sh + shape[2] + shape[3]))
+    x = r.standard_normal(shape, dtype=np.float32)
+    ho, wo = (shape[2] + 2 * ph - kh) // sh + 1, (shape[3] + 2 * pw - kw) // sw + 1
+    gy = r.standard_normal((shape[0], shape[1], ho, wo), dtype=np.float32)
+    _check(B, x, gy, geom, "%s %s" % (geom, shape))
+
+
+@pytest.mark.parametrize("geom", [(3, 3, 1, 1, 1, 1), (3, 3, 2, 2, 1, 1), (2, 2, 1, 1, 0, 0), (5, 3, 2, 1, 2, 1)])
+def test_ties_go_to_the_first_cell_and_integer_gradients_are_exact(B, geom):
+    """Planes of few distinct values: many windows hold their maximum more than once."""
+    kh, kw, sh, sw, ph, pw = geom
+    x = workloads.integer_valued((2, 3, 40, 45), 0, 2, 17)
+    ho, wo = (40 + 2 * ph - kh) // sh + 1, (45 + 2 * pw - kw) // sw + 1
+    gy = workloads.integer_valued((2, 3, ho, wo), -3, 3, 18)
+    gx, ref = _check(B, x, gy, geom, "ties %s" % (geom,))
+    assert np.array_equal(gx.astype(np.float64), ref)
+    flat = np.zeros((1, 1, 9, 9), np.float32)
+    ones = np.ones((1, 1, (9 + 2 * ph - kh) // sh + 1, (9 + 2 * pw - kw) // sw + 1), np.float32)
+    a = to_host(B.sws_maxpool2d_grad(to_gpu(flat), to_gpu(ones), *geom)).astype(np.float64)
+    assert np.array_equal(a, oracle.maxpool2d_grad(flat, ones, *geom))
+
+
+def test_direct_evaluation_kernel_and_conservation(B):
+    r = np.random.Generator(np.random.PCG64(5))
+    x = r.standard_normal((2, 2, 30, 33), dtype=np.float32)
+    gy = r.integers(-3, 4, (2, 2, 15, 17)).astype(np.float32)
+    B.sws_set_option("pool2d_variant", 1)
+    try:
+        gx, ref = _check(B, x, gy, (3, 3, 2, 2, 1, 1), "direct evaluation")
+    finally:
+        B.sws_set_option("pool2d_variant", 0)
+    assert np.array_equal(gx.astype(np.float64), ref)
+    assert np.array_equal(gx.astype(np.float64).sum(axis=(2, 3)), gy.astype(np.float64).sum(axis=(2, 3)))
+
+
+@pytest.mark.parametrize("stride", [1, 2])
+def test_cfg3_shaped_planes(B, stride):
+    x = workloads.make(3, x_shape=(2, 8, 112, 112))[0]
+    ho = (112 + 2 - 3) // stride + 1
+    gy = np.random.Generator(np.random.PCG64(stride)).standard_normal((2, 8, ho, ho), dtype=np.float32)
+    _check(B, x, gy, (3, 3, stride, stride, 1, 1), "cfg3 stride %d" % stride)
+
+
+def test_argument_checks(B):
+    import torch
+    x = torch.zeros((1, 2, 8, 8), device="cuda")
+    with pytest.raises(B.SwsError):
+        B.sws_maxpool2d_grad(x, torch.zeros((1, 2, 7, 7), device="cuda"), 3, 3, 1, 1, 1, 1)
+    assert B.lib().sws_maxpool2d_grad(x.data_ptr(), x.data_ptr(), None, 1, 2, 8, 8, 3, 3, 1, 1, 1, 1, None) == B.SWS_ERR_INVALID_ARG
+    assert B.lib().sws_maxpool2d_grad(x.data_ptr(), x.data_ptr(), x.data_ptr(), 1, 2, 8, 8, 3, 3, 1, 1, 3, 1, None) == B.SWS_ERR_INVALID_ARG
