@@ -309,6 +309,17 @@ def sweeps_table(torch, B, workloads, iters=20):
         ms = time_launches(torch, fn, iters)
         out["adjoints"][name] = {"us": round(ms * 1e3, 2), "TFLOPs": round(fl / ms / 1e9, 2),
                                  "frac_fp32_mfma_peak": round(fl / ms / 1e9 / 157.3, 4)}
+    x3 = g(workloads.make(3)[0])                          # configuration 3's max pooling: gradients routed to the maxima
+    gx3 = torch.empty_like(x3)
+    for st, ho in ((1, 112), (2, 56)):
+        gy3 = torch.empty(32, 64, ho, ho, device="cuda").normal_()
+        nb = 4 * 2048 * (2 * 112 * 112 + ho * ho)
+        ms = time_launches(torch, lambda: B.sws_maxpool2d_grad(x3, gy3, 3, 3, st, st, 1, 1, gx=gx3), iters)
+        out["adjoints"]["cfg3_maxpool3x3_s%d_grad" % st] = {"us": round(ms * 1e3, 2), "GBps": round(nb / ms / 1e6, 1),
+                                                           "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+        del gy3
+    del x3, gx3
+    torch.cuda.empty_cache()
     x4, w4 = workloads.make(4)
     x4, w4 = g(x4), g(w4)
     gy4 = torch.empty(32, 64, 56, 56, device="cuda").normal_()

@@ -178,3 +178,19 @@ def test_new_entry_points_argument_checks(L):
             (one, one, one, 1, 4, 32, 6, 3, 1, 0, 1, 1, nul))])
         assert g(groups=3) == 1 and g(k=0) == 1 and g(k=40) == 1 and g(stride=0) == 1 and g(c=nul) == 1
     assert L.sws_conv1d_grad_input(one, one, one, 0, 4, 32, 6, 3, 1, 0, 1, 1, nul) == 0
+    for f in (L.sws_conv2d_grad_input, L.sws_conv2d_grad_weight):
+        f.argtypes = [ctypes.c_void_p] * 3 + [i64] * 5 + [i32] * 6 + [ctypes.c_void_p]
+        g2 = lambda **kw: f(*[kw.get(n, v) for n, v in zip(
+            ("a", "b", "c", "N", "Cin", "H", "W", "Cout", "kh", "kw", "sh", "sw", "ph", "pw", "s"),
+            (one, one, one, 1, 4, 8, 8, 6, 3, 3, 1, 1, 1, 1, nul))])
+        assert g2(kh=0) == 1 and g2(sw=0) == 1 and g2(kh=11) == 1 and g2(c=nul) == 1 and g2(Cin=0) == 1
+    L.sws_maxpool2d_grad.argtypes = [ctypes.c_void_p] * 3 + [i64] * 4 + [i32] * 6 + [ctypes.c_void_p]
+    mp = lambda **kw: L.sws_maxpool2d_grad(*[kw.get(n, v) for n, v in zip(
+        ("x", "gy", "gx", "N", "C", "H", "W", "kh", "kw", "sh", "sw", "ph", "pw", "s"),
+        (one, one, one, 1, 3, 8, 8, 3, 3, 1, 1, 1, 1, nul))])
+    assert mp(N=0) == 0 and mp(ph=3) == 1 and mp(kw=0) == 1 and mp(gx=nul) == 1 and mp(kh=12) == 1
+    L.sws_pool2d_16.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, i64, i64, i64, i64,
+                                i32, i32, i32, i32, i32, i32, f32, ctypes.c_void_p]
+    assert L.sws_pool2d_16(0, 1, one, one, 0, 3, 8, 8, 3, 3, 1, 1, 1, 1, 1.0, nul) == 0
+    assert L.sws_pool2d_16(0, 3, one, one, 1, 3, 8, 8, 3, 3, 1, 1, 1, 1, 1.0, nul) == 1
+    assert L.sws_pool2d_16(0, 1, one, nul, 1, 3, 8, 8, 3, 3, 1, 1, 1, 1, 1.0, nul) == 1
