@@ -160,8 +160,8 @@ def ops_table(torch, B, workloads, iters=20):
     for s, ho in ((1, 112), (2, 56)):
         mk = lambda: (x3.clone(), torch.empty(32, 64, ho, ho, device="cuda"))
         nb = 4 * (2048 * 112 * 112 + 2048 * ho * ho)
-        record("cfg3_maxpool3x3_s%d" % s, lambda x, y: B.sws_pool2d(1, x, 3, 3, s, s, 1, 1, 1.0, y=y), mk, nb)
-        record("cfg3_avgpool3x3_s%d" % s, lambda x, y: B.sws_pool2d(0, x, 3, 3, s, s, 1, 1, 1 / 9, y=y), mk, nb)
+        record("cfg3_maxpool3x3_s%d" % s, lambda x, y: B.sws_pool2d(1, x, 3, 3, s, s, 1, 1, 1.0, y=y), mk, nb, graph=True)
+        record("cfg3_avgpool3x3_s%d" % s, lambda x, y: B.sws_pool2d(0, x, 3, 3, s, s, 1, 1, 1 / 9, y=y), mk, nb, graph=True)
     del x3
     # cfg4: conv2d [32,64,56,56] x [64,64,3,3], pad 1
     x4, w4 = workloads.make(4)
@@ -169,7 +169,7 @@ def ops_table(torch, B, workloads, iters=20):
     mk = lambda: (x4.clone(), torch.empty(32, 64, 56, 56, device="cuda"))
     nb = 4 * (2 * 32 * 64 * 56 * 56 + 64 * 64 * 9)
     record("cfg4_conv2d_3x3", lambda x, y: B.sws_conv2d(x, w4, 1, 1, 1, 1, y=y), mk, nb,
-           2.0 * 32 * 64 * 56 * 56 * 64 * 9)
+           2.0 * 32 * 64 * 56 * 56 * 64 * 9, graph=True)
     del x4
     torch.cuda.empty_cache()
     return out
