@@ -252,7 +252,7 @@ __global__ __launch_bounds__(kThreads) void pool2d_sep_kernel(const T *__restric
                                                               int W, int Ho, int Wo, int kh, int kw, int sh, int sw,
                                                               int ph, int pw, int P, int PC, int pwl, int TH, int bands,
                                                               float scale, int64_t n_units, int lds_floats,
-                                                              int in_rows, int div_valid)
+                                                              int in_rows, int div_valid, int ctiles, int TWO)
 {
     using O = Op<OP>;
     using IO = Io<T>;
@@ -260,20 +260,30 @@ __global__ __launch_bounds__(kThreads) void pool2d_sep_kernel(const T *__restric
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
     if (unit >= n_units) return;
+    // Planes whose rows do not fit the slice are cut into ctiles column tiles of TWO outputs each
+    // (ctiles = 1: the whole width).  A column tile stages the input columns its windows see,
+    // identity where they leave the plane, and needs no margins in `col` (pwl = 0, PC = P).
     // in:  [in_rows][P]  the input rows hv0 .. hv0 + in_rows - 1 of the band, rows outside the plane
     //                    (and columns W .. P-1) holding the identity, so that the loop over kh needs no bounds
     // col: [TH][PC]      those rows reduced down H, with pwl identity columns in front and enough
     //                    behind that the loop over kw needs none either
     float *in = lds_all + wave * lds_floats;
     float *col = in + in_rows * P;
-    const int64_t plane = unit / bands;
-    const int band = (int)(unit - plane * bands);
+    const bool tiled = ctiles > 1;
+    const int ct = (int)(unit % ctiles);
+    const int64_t pb = unit / ctiles;
+    const int64_t plane = pb / bands;
+    const int band = (int)(pb - plane * bands);
     const T *xp = x + plane * (int64_t)H * W;
     T *yp = y + plane * (int64_t)Ho * Wo;
     const int ho0 = band * TH;
     int ho1 = ho0 + TH;
     if (ho1 > Ho) ho1 = Ho;
     const int nr = ho1 - ho0;
+    const int wo0 = ct * TWO;                        // my outputs: columns wo0 .. wo1 - 1
+    const int wo1 = wo0 + TWO < Wo ? wo0 + TWO : Wo;
+    const int nwo = wo1 - wo0;
+    const int c_first = tiled ? wo0 * sw - pw : 0;   // plane column of staged column 0
     const int hv0 = ho0 * sh - ph;                   // first (possibly virtual) input row of the band
     const int rows_need = (nr - 1) * sh + kh;
     int row_lo = hv0 < 0 ? 0 : hv0, row_hi = hv0 + rows_need > H ? H : hv0 + rows_need;
@@ -284,7 +294,7 @@ __global__ __launch_bounds__(kThreads) void pool2d_sep_kernel(const T *__restric
     for (int i = lane; i < (row_lo - hv0) * P4; i += kWave) *(v4f *)(in + 4 * i) = id4;
     for (int i = (row_hi - hv0) * P4 + lane; i < rows_need * P4; i += kWave) *(v4f *)(in + 4 * i) = id4;
     float *in_real = in + (row_lo - hv0) * P;
-    if (P == W) {
+    if (P == W && !tiled) {
         // the real rows are one contiguous range: all its 128-bit loads are issued before the first
         // LDS write (lanes past the end re-read element 0 and drop it)
         const T *src = xp + (int64_t)row_lo * W;
@@ -304,9 +314,22 @@ __global__ __launch_bounds__(kThreads) void pool2d_sep_kernel(const T *__restric
     } else {
         const int n = (row_hi - row_lo) * P;
         const float inv_p = 1.0f / (float)P;
-        for (int i = lane; i < n; i += kWave) {
-            const int r = (int)(((float)i + 0.5f) * inv_p), c = i - r * P;
-            in_real[i] = (c < W) ? IO::load1(xp + (int64_t)(row_lo + r) * W + c) : O::id();
+        constexpr int U = 8;                         // eight loads per lane in flight
+        for (int i0 = 0; i0 < n; i0 += kWave * U) {
+            float v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + kWave * u + lane;
+                const int r = (int)(((float)i + 0.5f) * inv_p), c = c_first + i - r * P;
+                const bool ok = i < n && c >= 0 && c < W;
+                v[u] = IO::load1(xp + (ok ? (int64_t)(row_lo + r) * W + c : 0));
+                v[u] = ok ? v[u] : O::id();
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + kWave * u + lane;
+                if (i < n) in_real[i] = v[u];
+            }
         }
     }
     // identity margins of col: pwl columns in front, PC - pwl - P behind
@@ -338,10 +361,10 @@ __global__ __launch_bounds__(kThreads) void pool2d_sep_kernel(const T *__restric
     wave_lds_sync();
     // ---- along W: one output per lane, consecutive lanes on consecutive outputs (their LDS reads
     //      fall on consecutive banks, their stores on one contiguous run of y)
-    const float inv_wo = 1.0f / (float)Wo;
-    for (int item = lane; item < nr * Wo; item += kWave) {
-        const int r = (int)(((float)item + 0.5f) * inv_wo), wo = item - r * Wo;
-        const float *cr = col + r * PC + pwl - pw + wo * sw;
+    const float inv_wo = 1.0f / (float)nwo;
+    for (int item = lane; item < nr * nwo; item += kWave) {
+        const int r = (int)(((float)item + 0.5f) * inv_wo), wq = item - r * nwo, wo = wo0 + wq;
+        const float *cr = col + r * PC + (tiled ? wq * sw : pwl - pw + wo * sw);
         float acc = cr[0];
         int b = 1;
         for (; b + 4 <= kw; b += 4) {                // four reads in flight per wait
@@ -368,27 +391,42 @@ template <int OP, typename T>
 hipError_t launch_sep(const T *x, T *y, int64_t planes, int H, int W, int Ho, int Wo, int kh, int kw, int sh,
                       int sw, int ph, int pw, float scale, int div_valid, hipStream_t s, bool *taken)
 {
-    const int P = (W + 3) / 4 * 4;
-    const int pwl = (pw + 3) / 4 * 4;                // identity columns in front of a reduced row (kept 16-byte aligned)
+    const int budget = kSepLds / 4;
+    int P = (W + 3) / 4 * 4;
+    int pwl = (pw + 3) / 4 * 4;                      // identity columns in front of a reduced row (kept 16-byte aligned)
     int right = (Wo - 1) * sw - pw + kw - P;         // columns a window reaches beyond the staged pitch
     if (right < 0) right = 0;
-    const int PC = pwl + P + (right + 3) / 4 * 4;
+    int PC = pwl + P + (right + 3) / 4 * 4;
     // output rows per band: as many as the slice holds — (TH-1)*sh + kh staged rows of P floats plus
     // TH reduced rows of PC floats
-    const int budget = kSepLds / 4;
     int TH = (budget - (kh - sh) * P) / (sh * P + PC);
     if (TH > Ho) TH = Ho;
-    *taken = TH >= 1 && (int64_t)Ho * Wo < (1 << 20) && (int64_t)H * P < (1 << 20);
+    int ctiles = 1, TWO = Wo;
+    if (TH < 1) {
+        // the rows do not fit: column tiles.  A few output rows per band, the widest staged pitch the
+        // slice then allows, and as many outputs per tile as that pitch covers.
+        for (TH = Ho < 4 ? Ho : 4; TH >= 1; --TH) {
+            P = budget / ((TH - 1) * sh + kh + TH) / 4 * 4;
+            if (P >= kw + 15 * sw) break;            // at least 16 outputs per tile
+        }
+        if (TH >= 1) {
+            TWO = (P - kw) / sw + 1;
+            ctiles = (Wo + TWO - 1) / TWO;
+            pwl = 0;
+            PC = P;
+        }
+    }
+    *taken = TH >= 1 && (int64_t)Ho * Wo < (1LL << 40) && (int64_t)TH * (ctiles > 1 ? TWO : Wo) < (1 << 20);
     if (!*taken) return hipSuccess;
     const int in_rows = (TH - 1) * sh + kh;
     const int lds_floats = in_rows * P + TH * PC;
     const int bands = (Ho + TH - 1) / TH;
-    const int64_t n_units = planes * bands;
+    const int64_t n_units = planes * bands * ctiles;
     const int64_t grid = (n_units + kWaves - 1) / kWaves;
     if (grid > 2147483647LL) { *taken = false; return hipSuccess; }
     hipLaunchKernelGGL((pool2d_sep_kernel<OP, T>), dim3((unsigned)grid), dim3(kThreads), (size_t)lds_floats * 4 * kWaves, s,
                        x, y, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, P, PC, pwl, TH, bands, scale, n_units, lds_floats,
-                       in_rows, div_valid);
+                       in_rows, div_valid, ctiles, TWO);
     return hipGetLastError();
 }
 

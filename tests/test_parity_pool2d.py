@@ -76,8 +76,22 @@ def test_band_kernel_knobs(B, flags):
         B.sws_set_option("pool2d_variant", 0)
 
 
+@pytest.mark.parametrize("op", ["add", "max"])
+@pytest.mark.parametrize("geom,shape", [((1, 3, 1, 2, 0, 1), (2, 3, 1, 20001)), ((1, 9, 1, 1, 0, 4), (1, 2, 1, 50000)),
+                                        ((3, 3, 1, 1, 1, 1), (1, 2, 7, 5000)), ((5, 5, 2, 2, 2, 2), (1, 1, 30, 4001)),
+                                        ((2, 16, 2, 16, 0, 0), (1, 2, 6, 3200)), ((7, 7, 1, 3, 3, 3), (1, 1, 12, 9000))])
+def test_planes_wider_than_a_slice_are_cut_into_column_tiles(B, op, geom, shape):
+    """Rows too wide for a wavefront's LDS slice (and 1-D pooling with a stride, as planes of one row)."""
+    x = np.random.Generator(np.random.PCG64(shape[3] + geom[1])).standard_normal(shape, dtype=np.float32)
+    _check(B, op, x, *geom, what="wide %s %s %s" % (op, geom, shape))
+    y = to_host(B.sws_pool2d_ex(0, to_gpu(x), geom[0], geom[1], geom[2], geom[3], (geom[4], geom[5], 0, geom[1] - 1),
+                                B.SWS_DIV_REAL_CELLS, 1.0))
+    ref, mag = oracle.pool2d_ex(oracle.OP_ADD, x, geom[0], geom[1], geom[2], geom[3], (geom[4], geom[5], 0, geom[1] - 1), True, 1.0)
+    assert_within_tol(y, ref, mag, "wide pool2d_ex %s %s" % (geom, shape))
+
+
 def test_wide_plane_falls_back(B):
-    """A row too wide for a wavefront's LDS slice runs on the direct-evaluation kernel."""
+    """Wide rows with the specialised geometries (these used to run on the direct-evaluation kernel)."""
     x = np.random.Generator(np.random.PCG64(8)).standard_normal((1, 2, 9, 3000), dtype=np.float32)
     _check(B, "max", x, 3, 3, 1, 1, 1, 1)
     _check(B, "add", x, 3, 3, 2, 2, 1, 1)
