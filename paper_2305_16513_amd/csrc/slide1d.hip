@@ -160,11 +160,15 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
     // The row the windows slide over is the physical row of `len` elements extended to `lv`
     // (pad_left in front, the rest behind) by the boundary rule pad_mode; lo = lv - S outputs.
     // The plain instantiation sees constants, so the common path carries none of this.
-    constexpr bool PADDED = MODE == 1;
-    const int pad_left = PADDED ? pad_left_arg : 0, pad_mode = PADDED ? pad_mode_arg : SWS_PAD_IDENTITY;
+    // MODE 3: a chain link over extended rows — pad_left may then be negative (the link's windows
+    // start inside the row), pad_mode_arg carries the boundary rule in its low byte and the
+    // "combine with y" flag in bit 8.
+    constexpr bool PADDED = MODE == 1 || MODE == 3;
+    constexpr bool CHAIN = MODE == 2 || MODE == 3;
+    const int pad_left = PADDED ? pad_left_arg : 0, pad_mode = PADDED ? (pad_mode_arg & 255) : SWS_PAD_IDENTITY;
     const int lv = PADDED ? lv_arg : len;
     const int pitch = MODE == 2 ? lv_arg : len;     // distance between rows of x
-    const bool chain_acc = MODE == 2 && (pad_mode_arg & 1);   // combine with the earlier links' result in y
+    const bool chain_acc = (MODE == 2 && (pad_mode_arg & 1)) || (MODE == 3 && (pad_mode_arg & 256));   // combine with the earlier links' result in y
     using O = Op<OP>;
     using G = SegStep<OP>;
     static_assert(C == 16, "the LDS layout assumes 16-element chunks");
@@ -334,7 +338,7 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
             }
             v4f o;
             o.x = O::f(s4v.x, pn.x); o.y = O::f(s4v.y, pn.y); o.z = O::f(s4v.z, pn.z); o.w = O::f(s4v.w, pn.w);
-            if (MODE != 2) {
+            if (!CHAIN) {
                 if (PADDED && OP == SWS_OP_ADD && pad_mode == SWS_PAD_SHRINK) {
                     // the window shrinks at the ends of the row: rescale by w / (real elements in it)
                     float ov[4] = {o.x, o.y, o.z, o.w};
@@ -439,7 +443,11 @@ hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, 
     const int64_t n_units = (n_tiles + g - 1) / g;
     const int64_t grid = remap ? xcd_grid(n_units) : n_units;
     if (grid > 2147483647LL) return hipErrorInvalidValue;
-    if (chain) {                                      // chain bits: 1 = combine with y, 2 = last link
+    if (chain & 8) {                                  // a link over extended rows (chain bits: 1 = combine with y, 2 = last)
+        if (!(chain & 2)) flags &= ~2;
+        hipLaunchKernelGGL((slide_scan_kernel<OP, C, 3>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
+                           S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, pad_left, pad_mode | ((chain & 1) << 8), lv);
+    } else if (chain) {                               // chain bits: 1 = combine with y, 2 = last link
         if (!(chain & 2)) flags &= ~2;                // y is read again by the next link: plain stores
         hipLaunchKernelGGL((slide_scan_kernel<OP, C, 2>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
                            S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, 0, chain & 1, pitch);
@@ -479,6 +487,28 @@ hipError_t launch_chain(const float *x, float *y, int64_t rows, int len, int lo,
     return hipSuccess;
 }
 
+// The same over rows extended by a boundary rule: link j slides its window over the extended row
+// from element off_j = w_0 + ... + w_{j-1} on, i.e. with pad_left - off_j elements in front (negative
+// once the link starts inside the row) and an extended length of lo + w_j - 1.
+template <int OP>
+hipError_t launch_chain_padded(const float *x, float *y, int64_t rows, int len, int lo, int w, int pad_left, int pad_mode,
+                               float scale, hipStream_t s)
+{
+    const int reach = 768;
+    int links = (w + reach - 1) / reach;
+    if (links < 2) links = 2;
+    int done = 0;
+    for (int j = 0; j < links; ++j) {
+        const int wj = (w - done) / (links - j);
+        const bool last = j == links - 1;
+        const hipError_t e = launch_scan<OP>(x, y, rows, len, lo, wj, last ? scale : 1.0f, pad_left - done, pad_mode,
+                                             lo + wj - 1, s, 8 | 4 | (j > 0 ? 1 : 0) | (last ? 2 : 0), 0);
+        if (e != hipSuccess) return e;
+        done += wj;
+    }
+    return hipSuccess;
+}
+
 constexpr int kDirectMaxW = 9;
 constexpr int kScanMaxW = kWave * 16 - 64 + 1;      // leaves at least 64 outputs per wave tile
 constexpr int kChainMinW = 850;                     // longer windows run as a chain of shorter ones
@@ -504,7 +534,8 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
         // 16384-long rows 0.76-0.77 against 0.73-0.76; cfg 1 in a HIP graph 3.0-3.4 us against 4.3.
         const bool small_w = w <= kDirectMaxW && (lo <= 8192 || rows * len64 <= (8LL << 20));
         if (w == 1) variant = padded ? 1 : 2;
-        else if (padded) variant = w <= kScanMaxW ? 3 : 1;
+        else if (padded && pad_mode == SWS_PAD_SHRINK) variant = w <= kScanMaxW ? 3 : 1;   // one pass rescales by the real elements
+        else if (padded) variant = w <= kChainMinW ? 3 : 6;   // 6: a chain over extended rows
         else if (small_w) variant = 2;
         else variant = w <= kChainMinW ? 3 : 5;
     }
@@ -514,6 +545,13 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
             case SWS_OP_ADD: return launch_chain<SWS_OP_ADD>(x, y, rows, len, lo, w, scale, s);
             case SWS_OP_MAX: return launch_chain<SWS_OP_MAX>(x, y, rows, len, lo, w, scale, s);
             default: return launch_chain<SWS_OP_MIN>(x, y, rows, len, lo, w, scale, s);
+        }
+    }
+    if (variant == 6) {
+        switch (op) {
+        case SWS_OP_ADD: return launch_chain_padded<SWS_OP_ADD>(x, y, rows, len, lo, w, pad_left, pad_mode, scale, s);
+        case SWS_OP_MAX: return launch_chain_padded<SWS_OP_MAX>(x, y, rows, len, lo, w, pad_left, pad_mode, scale, s);
+        default: return launch_chain_padded<SWS_OP_MIN>(x, y, rows, len, lo, w, pad_left, pad_mode, scale, s);
         }
     }
     if (variant == 1) return launch_slide1d_naive(op, x, y, rows, len64, w, pad_left, pad_right, pad_mode, scale, s);

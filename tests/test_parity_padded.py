@@ -56,6 +56,16 @@ def test_padded_short_rows_and_extreme_pads(B, mode):
             _check(B, op, x, w, pl, pr, mode, "short len=%d w=%d pads=(%d,%d) mode=%d op=%d" % (length, w, pl, pr, mode, op))
 
 
+@pytest.mark.parametrize("mode", [0, 1, 2, 3])
+@pytest.mark.parametrize("op", [0, 1, 2])
+@pytest.mark.parametrize("w,pl,pr,length", [(962, 481, 480, 3000), (2000, 999, 1000, 5003), (2049, 0, 2048, 2100), (5000, 4000, 999, 6001),
+                                            (1500, 1499, 0, 1600)])
+def test_padded_windows_longer_than_a_tile_run_as_a_chain_over_the_extended_row(B, mode, op, w, pl, pr, length):
+    r = _rng(mode * 7 + op * 3 + w)
+    x = (r.random((3, length), dtype=np.float32) * 2 - 1).astype(np.float32)
+    _check(B, op, x, w, pl, pr, mode, "chain mode=%d op=%d w=%d pads=(%d,%d) len=%d" % (mode, op, w, pl, pr, length))
+
+
 def test_padded_zero_pads_match_the_unpadded_entry_point(B):
     r = _rng(44)
     x = r.standard_normal((5, 2500), dtype=np.float32)
