@@ -262,3 +262,43 @@ def test_longest_supported_row(B):
     del x
     torch.cuda.empty_cache()
     assert B.lib().sws_slide1d(0, 16, 16, 1, length + 1, 16, 1.0, None) == B.SWS_ERR_INVALID_ARG
+
+
+def test_more_than_2_to_the_32_elements(B):
+    """70 000 rows of 65 536 (4.6e9 elements, 18 GB in): every row offset beyond 2^31 and 2^32 elements
+    must be computed in 64 bits.  The oracle checks the first and last rows and those around the
+    2^31- and 2^32-element marks, for the scan kernel (fp32 and bf16), the shifted-load kernel and the
+    thin convolution."""
+    import torch
+    rows, length = 70000, 65536
+    free, _ = torch.cuda.mem_get_info()
+    if free < 4 * rows * length * 2.3:
+        pytest.skip("not enough device memory")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(32)
+    x = torch.rand(rows, length, device="cuda", generator=g) * 2 - 1
+    sample = [0, 1, 32767, 32768, 32769, 65535, 65536, 65537, rows - 2, rows - 1]
+    xs = to_host(x[sample])
+    for op, w in ((0, 64), (1, 5), (0, 900)):
+        y = B.sws_slide1d(op, x, w, 1.0)
+        ref, mag = oracle.slide1d(op, xs, w, 1.0)
+        got = to_host(y[sample])
+        del y
+        if op == 0:
+            assert_within_tol(got, ref, mag, "big add w=%d" % w)
+        else:
+            assert_bit_exact(got, ref, "big max w=%d" % w)
+    xc = x.view(rows // 2, 2, length)                                     # [35000, 2, 65536], depthwise, two channels
+    t2 = np.random.Generator(np.random.PCG64(34)).standard_normal((2, 1, 9), dtype=np.float32)
+    y = B.sws_conv1d(xc, to_gpu(t2), groups=2)
+    for b in (0, 16384, 32768, rows // 2 - 1):
+        ref, mag = oracle.conv1d(to_host(xc[b:b + 1]), t2, groups=2)
+        assert_within_tol(to_host(y[b:b + 1]), ref, mag, "big depthwise conv image %d" % b)
+    del y
+    xb = x.to(torch.bfloat16)
+    del x
+    y = B.sws_slide1d_16(1, xb, 33, 1.0)
+    ref, _ = oracle.slide1d(1, xb[sample].float().cpu().numpy(), 33, 1.0)
+    assert np.array_equal(y[sample].float().cpu().numpy().astype(np.float64), ref)
+    del y, xb
+    torch.cuda.empty_cache()
