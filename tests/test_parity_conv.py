@@ -336,3 +336,37 @@ def test_cfg4_conv2d_full_size(B):
     ref, mag = oracle.conv2d(x[imgs], w, 1, 1, 1, 1)
     assert_within_tol(y[imgs], ref, mag, "cfg4 conv2d")
     assert np.isfinite(y).all()
+
+
+def test_conv2d_more_than_2_to_the_32_elements(B):
+    """22 000 images of [64, 56, 56] (4.4e9 elements): image offsets beyond 2^32 elements in the matrix kernel
+    and in both adjoints."""
+    import torch
+    n = 22000
+    free, _ = torch.cuda.mem_get_info()
+    if free < 4 * n * 64 * 56 * 56 * 3.3:
+        pytest.skip("not enough device memory")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(43)
+    x = torch.randn(n, 64, 56, 56, device="cuda", generator=g)
+    w = (_rng(44).standard_normal((64, 64, 3, 3), dtype=np.float32) * np.float32(0.06)).astype(np.float32)
+    y = B.sws_conv2d(x, to_gpu(w), 1, 1, 1, 1)
+    sample = [0, 10699, 10700, 21399, 21400, n - 1]                       # around the 2^31- and 2^32-element marks
+    for i in sample:
+        ref, mag = oracle.conv2d(to_host(x[i:i + 1]), w, 1, 1, 1, 1)
+        assert_within_tol(to_host(y[i:i + 1]), ref, mag, "big conv2d image %d" % i)
+    gx = B.sws_conv2d_grad_input(y, to_gpu(w), 56, 56, 1, 1, 1, 1)
+    for i in (0, 21400, n - 1):
+        ref, mag = oracle.conv2d_grad_input(to_host(y[i:i + 1]), w, 56, 56, 1, 1, 1, 1)
+        assert_within_tol(to_host(gx[i:i + 1]), ref, mag, "big conv2d grad-input image %d" % i)
+    del gx
+    # grad-weight sums over every image: compare with the sum over the same three images given alone
+    idx = torch.tensor([0, 21400, n - 1], device="cuda")
+    xs, ys = x[idx].contiguous(), y[idx].contiguous()
+    y.zero_()
+    y[idx] = ys                                                           # gradients only at the three images
+    gw = to_host(B.sws_conv2d_grad_weight(x, y, 3, 3, 1, 1, 1, 1))
+    ref, mag = oracle.conv2d_grad_weight(to_host(xs), to_host(ys), 3, 3, 1, 1, 1, 1)
+    assert_within_tol(gw, ref, mag, "big conv2d grad-weight")
+    del x, y
+    torch.cuda.empty_cache()

@@ -167,3 +167,33 @@ def test_pool2d_ex_equal_pads_match_pool2d_and_argument_checks(B):
         B.sws_pool2d_ex(0, x, 3, 3, 1, 1, (3, 0, 0, 0))
     with pytest.raises(B.SwsError):
         B.sws_pool2d_ex(0, x, 3, 3, 1, 1, (0, 0, 0, 0), 5)
+
+
+def test_more_than_2_to_the_32_elements(B):
+    """349 952 planes of 112 x 112 (4.4e9 elements): plane offsets beyond 2^32 elements, for the
+    specialised band kernel, the run-time separable kernel and the max-pooling adjoint."""
+    import torch
+    planes = 349952                                                       # 5468 x 64
+    free, _ = torch.cuda.mem_get_info()
+    if free < 4 * planes * 112 * 112 * 3.3:
+        pytest.skip("not enough device memory")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(41)
+    x = torch.randn(planes // 64, 64, 112, 112, device="cuda", generator=g)
+    flat = x.view(planes, 112, 112)
+    sample = [0, 171195, 171196, 342392, 342393, planes - 1]              # around the 2^31- and 2^32-element marks
+    xs = to_host(flat[sample]).reshape(1, len(sample), 112, 112)
+    for kh, kw, sh, sw, ph, pw in ((3, 3, 2, 2, 1, 1), (4, 4, 4, 4, 0, 0)):
+        y = B.sws_pool2d(1, x, kh, kw, sh, sw, ph, pw, 1.0)
+        ref, _ = oracle.pool2d(oracle.OP_MAX, xs, kh, kw, sh, sw, ph, pw)
+        got = to_host(y.view(planes, y.shape[2], y.shape[3])[sample])
+        assert_bit_exact(got.reshape(ref.shape), ref, "big max pool %dx%d" % (kh, kw))
+        del y
+    gy = torch.randn(planes // 64, 64, 56, 56, device="cuda", generator=g)
+    gx = B.sws_maxpool2d_grad(x, gy, 3, 3, 2, 2, 1, 1)
+    gys = to_host(gy.view(planes, 56, 56)[sample]).reshape(1, len(sample), 56, 56)
+    ref = oracle.maxpool2d_grad(xs, gys, 3, 3, 2, 2, 1, 1)
+    mag = oracle.maxpool2d_grad(xs, np.abs(gys), 3, 3, 2, 2, 1, 1)
+    assert_within_tol(to_host(gx.view(planes, 112, 112)[sample]).reshape(ref.shape), ref, mag, "big max pool adjoint")
+    del x, gy, gx
+    torch.cuda.empty_cache()
