@@ -416,6 +416,13 @@ def run_only(torch, B, workloads, name, steps):
         y = torch.empty(16, 64, 4094, device="cuda")
         op = 1 if "max" in name else 0
         fn = lambda: B.sws_slide1d(op, x2, 3, 1 / 3, y=y)
+    elif name in ("grad_cfg3_maxpool_s1", "grad_cfg3_maxpool_s2"):
+        x3 = g(workloads.make(3)[0])
+        s = int(name[-1])
+        ho = 112 if s == 1 else 56
+        gy = torch.empty(32, 64, ho, ho, device="cuda").normal_()
+        gx = torch.empty_like(x3)
+        fn = lambda: B.sws_maxpool2d_grad(x3, gy, 3, 3, s, s, 1, 1, gx=gx)
     elif name.startswith("cfg3_"):
         x3 = g(workloads.make(3)[0])
         s = int(name[-1])
