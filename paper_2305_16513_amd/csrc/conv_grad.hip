@@ -228,9 +228,17 @@ struct GwGeom {
     int Cin, Cout, L, Lo, k, pad, dilation;          // row lengths of x and gy, taps per kernel row, left padding
     int H, Ho, kh, sh, ph;                           // rows of x and gy per image, kernel rows, row stride, top padding
     int64_t x_cs, gy_cs;                             // channel strides (H*L, Ho*Lo)
+    int segp, nseg;                                  // packed mode: positions per row segment, row segments per slab
+    int64_t rows_total;                              // packed mode: images * Ho
 };
 
-template <int KT, int XC>
+// PACK: rows shorter than half a slab.  A slab then holds nseg row segments of segp = Lo + (KT-1)*d
+// positions each: segment s is (image, output row) number slab*nseg + s, its gy values followed by
+// (KT-1)*d zeros, and beside it the x positions those outputs meet, so that position p + t*d of the x
+// slice is still the tap-t partner of position p of the gy slice.  What the zeros of gy multiply is
+// real x data or zero, never stale LDS.  (Without it a 14-wide row would fill 14 of a slab's 64
+// positions.)
+template <int KT, int XC, bool PACK = false>
 __global__ __launch_bounds__(kThreads) void conv1d_dense_grad_weight_kernel(
     const float *__restrict__ x, const float *__restrict__ gy, float *__restrict__ gw, GwGeom gm, int XPITCH,
     int slabs_per_row, int64_t total_slabs, int slabs, int co_blocks, int ci_blocks, int tap_groups)
@@ -279,7 +287,7 @@ __global__ __launch_bounds__(kThreads) void conv1d_dense_grad_weight_kernel(
         r.w = (row_ok && j + 3 >= 0 && j + 3 < n) ? row[j + 3] : 0.0f;
         return r;
     };
-    auto prefetch = [&](int64_t slab) {
+    auto prefetch_rows = [&](int64_t slab) {
         const int64_t rho = slab / slabs_per_row;    // (image, output row)
         const int i0 = (int)(slab - rho * slabs_per_row) * kPw;
         const int j0 = i0 + t0 * dilation - pad;
@@ -296,7 +304,55 @@ __global__ __launch_bounds__(kThreads) void conv1d_dense_grad_weight_kernel(
             greg[p] = load4(gyb + (co < Cout ? co : 0) * gm.gy_cs, i0 + scol, Lo, co < Cout);
 #pragma unroll
             for (int c = 0; c < XCMAX; ++c) {
-                xreg[c][p] = load4(xb_ + (ci < Cin ? ci : 0) * gm.x_cs, j0 + 64 * c + scol, L, h_ok && ci < Cin);
+                // lanes whose four columns lie beyond the staged width load nothing
+                xreg[c][p] = load4(xb_ + (ci < Cin ? ci : 0) * gm.x_cs, j0 + 64 * c + scol, L,
+                                   h_ok && ci < Cin && 64 * c + scol < xw);
+            }
+        }
+    };
+    // packed mode: which (segment, offset) each of my columns is does not change from slab to slab
+    auto prefetch_packed = [&](int64_t slab) {
+        const int64_t rho0 = slab * gm.nseg;
+        const int64_t b0 = rho0 / gm.Ho;
+        const int ho0 = (int)(rho0 - b0 * gm.Ho);
+        int64_t goff[4], xoff[XCMAX][4];
+        bool gok[4], xok[XCMAX][4];
+#pragma unroll
+        for (int c = 0; c <= XCMAX; ++c)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int q = (c == 0 ? 0 : 64 * (c - 1)) + scol + e;     // c = 0: gy columns; c >= 1: x column block c - 1
+                const int sg = q / gm.segp, o = q - sg * gm.segp;
+                const int tr = ho0 + sg;
+                const int64_t b = b0 + tr / gm.Ho;
+                const int ho = tr % gm.Ho;
+                const bool seg_ok = sg < gm.nseg && rho0 + sg < gm.rows_total;
+                if (c == 0) {
+                    gok[e] = seg_ok && o < Lo;
+                    goff[e] = b * Cout * gm.gy_cs + (int64_t)ho * Lo + o;
+                } else {
+                    const int col = t0 * dilation - pad + o;
+                    const int h = ho * gm.sh - gm.ph + ka;
+                    xok[c > 0 ? c - 1 : 0][e] = seg_ok && q < xw && col >= 0 && col < L && h >= 0 && h < gm.H;
+                    xoff[c > 0 ? c - 1 : 0][e] = b * Cin * gm.x_cs + (int64_t)h * L + col;
+                }
+            }
+#pragma unroll
+        for (int p = 0; p < GV; ++p) {
+            const int row = 4 * p + srow;
+            const int co = co0 + row, ci = ci0 + row;
+            const float *gr = gy + (co < Cout ? co : 0) * gm.gy_cs;
+            const float *xr = x + (ci < Cin ? ci : 0) * gm.x_cs;
+            greg[p].x = (gok[0] && co < Cout) ? gr[goff[0]] : 0.0f;
+            greg[p].y = (gok[1] && co < Cout) ? gr[goff[1]] : 0.0f;
+            greg[p].z = (gok[2] && co < Cout) ? gr[goff[2]] : 0.0f;
+            greg[p].w = (gok[3] && co < Cout) ? gr[goff[3]] : 0.0f;
+#pragma unroll
+            for (int c = 0; c < XCMAX; ++c) {
+                xreg[c][p].x = (xok[c][0] && ci < Cin) ? xr[xoff[c][0]] : 0.0f;
+                xreg[c][p].y = (xok[c][1] && ci < Cin) ? xr[xoff[c][1]] : 0.0f;
+                xreg[c][p].z = (xok[c][2] && ci < Cin) ? xr[xoff[c][2]] : 0.0f;
+                xreg[c][p].w = (xok[c][3] && ci < Cin) ? xr[xoff[c][3]] : 0.0f;
             }
         }
     };
@@ -319,11 +375,17 @@ __global__ __launch_bounds__(kThreads) void conv1d_dense_grad_weight_kernel(
     };
 
     int64_t slab = slab0 + wave;
-    if (slab < slab1) prefetch(slab);
+    if (slab < slab1) {
+        if constexpr (PACK) prefetch_packed(slab);
+        else prefetch_rows(slab);
+    }
     for (; slab < slab1; slab += kWavesPerWg) {
         commit();
         wave_lds_sync();
-        if (slab + kWavesPerWg < slab1) prefetch(slab + kWavesPerWg);     // in flight during the matrix work
+        if (slab + kWavesPerWg < slab1) {            // in flight during the matrix work
+            if constexpr (PACK) prefetch_packed(slab + kWavesPerWg);
+            else prefetch_rows(slab + kWavesPerWg);
+        }
         const float *ga = Gl + l32 * kGPitch + half;
         const float *xb = Xl + l32 * XPITCH + half;
 #pragma unroll 4
@@ -375,9 +437,10 @@ hipError_t launch_thin_gw(const float *x, const float *gy, float *gw, int B, int
 }
 
 template <int KT>
-hipError_t launch_dense_gw(const float *x, const float *gy, float *gw, int64_t B, const GwGeom &gm, hipStream_t s,
+hipError_t launch_dense_gw(const float *x, const float *gy, float *gw, int64_t B, const GwGeom &gm_in, hipStream_t s,
                            bool *taken)
 {
+    GwGeom gm = gm_in;
     const int xw = kPw + (KT - 1) * gm.dilation;
     const int XPITCH = (xw + 61) / 64 * 64 + 2;      // >= xw, = 2 mod 64
     const size_t stage = (size_t)kWavesPerWg * (32 * kGPitch + 32 * XPITCH) * sizeof(float);
@@ -386,7 +449,12 @@ hipError_t launch_dense_gw(const float *x, const float *gy, float *gw, int64_t B
     *taken = lds <= 128 * 1024 && xw <= 256;        // above 64 KB the kernel's LDS limit is raised below
     if (!*taken) return hipSuccess;
     const int slabs_per_row = (gm.Lo + kPw - 1) / kPw;
-    const int64_t total_slabs = B * gm.Ho * slabs_per_row;
+    // rows of at most half a slab (with their tap margin) are packed several to a slab
+    gm.segp = gm.Lo + (KT - 1) * gm.dilation;
+    gm.nseg = kPw / gm.segp;
+    gm.rows_total = B * gm.Ho;
+    const bool pack = gm.nseg >= 2 && xw <= 128 && g_opt.conv2d_variant != 3;
+    const int64_t total_slabs = pack ? (gm.rows_total + gm.nseg - 1) / gm.nseg : B * gm.Ho * slabs_per_row;
     const int co_blocks = (gm.Cout + 31) / 32, ci_blocks = (gm.Cin + 31) / 32;
     const int tap_groups = gm.kh * ((gm.k + KT - 1) / KT);
     const int64_t blocks = (int64_t)co_blocks * ci_blocks * tap_groups;
@@ -401,20 +469,27 @@ hipError_t launch_dense_gw(const float *x, const float *gy, float *gw, int64_t B
     if (g_opt.slide_group > 0) slabs = g_opt.slide_group;           // A/B: slabs per workgroup
     const int64_t grid = blocks * ((total_slabs + slabs - 1) / slabs);
     if (grid > 2147483647LL || slabs > 2147483647LL) { *taken = false; return hipSuccess; }
-#define SWS_DGW(XC)                                                                                               \
+#define SWS_DGW(XC, PACK)                                                                                         \
     case XC:                                                                                                      \
         if (lds > 64 * 1024) {                                                                                    \
-            const hipError_t ea = hipFuncSetAttribute((const void *)conv1d_dense_grad_weight_kernel<KT, XC>,      \
+            const hipError_t ea = hipFuncSetAttribute((const void *)conv1d_dense_grad_weight_kernel<KT, XC, PACK>, \
                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);      \
             if (ea != hipSuccess) return ea;                                                                      \
         }                                                                                                         \
-        hipLaunchKernelGGL((conv1d_dense_grad_weight_kernel<KT, XC>), dim3((unsigned)grid), dim3(kThreads), lds, s, x, \
-                           gy, gw, gm, XPITCH, slabs_per_row, total_slabs, (int)slabs, co_blocks, ci_blocks,      \
+        hipLaunchKernelGGL((conv1d_dense_grad_weight_kernel<KT, XC, PACK>), dim3((unsigned)grid), dim3(kThreads), lds, \
+                           s, x, gy, gw, gm, XPITCH, slabs_per_row, total_slabs, (int)slabs, co_blocks, ci_blocks, \
                            tap_groups);                                                                           \
         break
-    switch ((xw + 63) / 64) {
-        SWS_DGW(1); SWS_DGW(2); SWS_DGW(3); SWS_DGW(4);
-    default: *taken = false; return hipSuccess;
+    if (pack) {
+        switch ((xw + 63) / 64) {
+            SWS_DGW(1, true); SWS_DGW(2, true);
+        default: *taken = false; return hipSuccess;
+        }
+    } else {
+        switch ((xw + 63) / 64) {
+            SWS_DGW(1, false); SWS_DGW(2, false); SWS_DGW(3, false); SWS_DGW(4, false);
+        default: *taken = false; return hipSuccess;
+        }
     }
 #undef SWS_DGW
     return hipGetLastError();

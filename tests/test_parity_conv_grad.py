@@ -178,6 +178,40 @@ def test_conv2d_adjoints(B, case, integer):
         assert_within_tol(gw, rw, mw, "conv2d grad_weight %s" % (case,))
 
 
+# short rows: several (image, output row) pairs share one 64-position slab of the dense grad-weight
+# kernel; in the third case a slab holds more rows than an image has, in the last the rows are images
+SHORT_ROWS_2D = [(3, 40, 7, 7, 33, 3, 3, 1, 1, 1, 1), (5, 16, 14, 14, 16, 3, 3, 1, 1, 1, 1), (33, 8, 5, 6, 8, 3, 3, 1, 1, 1, 1),
+                 (2, 64, 28, 28, 64, 3, 3, 1, 1, 1, 1), (7, 12, 3, 30, 20, 1, 5, 1, 1, 0, 2), (4, 8, 9, 4, 8, 3, 3, 1, 1, 1, 1)]
+SHORT_ROWS_1D = [(37, 16, 12, 24, 3, 1, 1, 1, 1), (40, 8, 9, 8, 2, 1, 0, 3, 1), (9, 32, 31, 32, 1, 1, 0, 1, 1), (70, 8, 6, 8, 4, 1, 2, 1, 1)]
+
+
+@pytest.mark.parametrize("integer", [False, True])
+@pytest.mark.parametrize("case", SHORT_ROWS_2D)
+def test_conv2d_adjoints_short_rows(B, case, integer):
+    test_conv2d_adjoints(B, case, integer)
+
+
+@pytest.mark.parametrize("case", SHORT_ROWS_1D)
+def test_conv1d_adjoints_short_rows(B, case):
+    test_grad_weight(B, case)
+    test_grad_input(B, case)
+    test_exact_on_small_integers(B, case)
+
+
+def test_packed_and_unpacked_slabs_agree(B):
+    """The dense grad-weight kernel with and without row packing (option conv2d_variant = 3 turns it off)."""
+    case = SHORT_ROWS_2D[1]
+    n, cin, h, wd, cout, kh, kw, sh, sw, ph, pw = case
+    x, w, g = _data2d(case, 77, integer=True)
+    packed = to_host(B.sws_conv2d_grad_weight(to_gpu(x), to_gpu(g), kh, kw, sh, sw, ph, pw))
+    B.sws_set_option("conv2d_variant", 3)
+    try:
+        plain = to_host(B.sws_conv2d_grad_weight(to_gpu(x), to_gpu(g), kh, kw, sh, sw, ph, pw))
+    finally:
+        B.sws_set_option("conv2d_variant", 0)
+    assert np.array_equal(packed, plain)
+
+
 def test_conv2d_adjoints_direct_evaluation_kernels(B):
     B.sws_set_option("conv2d_variant", 1)
     try:
