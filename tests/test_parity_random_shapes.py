@@ -244,3 +244,42 @@ def test_pool2d_ex_random(B, seed):
         assert_within_tol(y, ref, mag, what)
     else:
         assert_bit_exact(y, ref, what)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_maxpool2d_grad_random(B, seed):
+    """Windows, strides and paddings drawn at random (strides above the window included: cells no
+    window covers get zero), planes from a few cells to several bands, few distinct values (ties)."""
+    r = _rng(7900 + seed)
+    kh, kw = int(r.integers(1, 7)), int(r.integers(1, 7))
+    sh, sw = int(r.integers(1, 5)), int(r.integers(1, 5))
+    ph, pw = int(r.integers(0, kh)), int(r.integers(0, kw))
+    h = max(1, kh - 2 * ph) + int(r.integers(0, 130))
+    wd = max(1, kw - 2 * pw) + int(r.integers(0, 300 if seed % 4 else 1500))
+    n, c = int(r.integers(1, 3)), int(r.integers(1, 4))
+    ho, wo = (h + 2 * ph - kh) // sh + 1, (wd + 2 * pw - kw) // sw + 1
+    x = r.integers(0, 6 if seed % 2 else 1000, (n, c, h, wd)).astype(np.float32)
+    gy = r.standard_normal((n, c, ho, wo), dtype=np.float32)
+    gx = to_host(B.sws_maxpool2d_grad(to_gpu(x), to_gpu(gy), kh, kw, sh, sw, ph, pw))
+    ref = oracle.maxpool2d_grad(x, gy, kh, kw, sh, sw, ph, pw)
+    mag = oracle.maxpool2d_grad(x, np.abs(gy), kh, kw, sh, sw, ph, pw)
+    assert_within_tol(gx, ref, mag, "seed %d: %dx%d s%dx%d p%dx%d plane %dx%d" % (seed, kh, kw, sh, sw, ph, pw, h, wd))
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_conv2d_grad_weight_short_rows_random(B, seed):
+    """Planes narrow enough that the dense kernel packs several output rows into one slab."""
+    r = _rng(8000 + seed)
+    cin, cout = int(r.integers(2, 70)), int(r.integers(1, 70))
+    kh, kw = int(r.integers(1, 6)), int(r.integers(1, 6))
+    sh = int(r.integers(1, 3))
+    ph, pw = int(r.integers(0, kh)), int(r.integers(0, kw))
+    h = max(1, kh - 2 * ph) + int(r.integers(0, 20))
+    wd = max(1, kw - 2 * pw) + int(r.integers(0, 30))
+    n = int(r.integers(1, 12))
+    ho, wo = (h + 2 * ph - kh) // sh + 1, (wd + 2 * pw - kw) + 1
+    x = r.standard_normal((n, cin, h, wd), dtype=np.float32)
+    g = r.standard_normal((n, cout, ho, wo), dtype=np.float32)
+    gw = to_host(B.sws_conv2d_grad_weight(to_gpu(x), to_gpu(g), kh, kw, sh, 1, ph, pw))
+    rw, mw = oracle.conv2d_grad_weight(x, g, kh, kw, sh, 1, ph, pw)
+    assert_within_tol(gw, rw, mw, "seed %d: N %d Cin %d H %d W %d Cout %d k %dx%d sh %d p %dx%d" % (seed, n, cin, h, wd, cout, kh, kw, sh, ph, pw))
