@@ -227,6 +227,7 @@ constexpr int kGPitch = kPw + 2;
 struct GwGeom {
     int Cin, Cout, L, Lo, k, pad, dilation;          // row lengths of x and gy, taps per kernel row, left padding
     int H, Ho, kh, sh, ph;                           // rows of x and gy per image, kernel rows, row stride, top padding
+    int sw;                                          // stride along the row (1 or 2)
     int64_t x_cs, gy_cs;                             // channel strides (H*L, Ho*Lo)
     int segp, nseg;                                  // packed mode: positions per row segment, row segments per slab
     int64_t rows_total;                              // packed mode: images * Ho
@@ -238,7 +239,9 @@ struct GwGeom {
 // slice is still the tap-t partner of position p of the gy slice.  What the zeros of gy multiply is
 // real x data or zero, never stale LDS.  (Without it a 14-wide row would fill 14 of a slab's 64
 // positions.)
-template <int KT, int XC, bool PACK = false>
+// SW: stride along the row.  gy position p meets x position p*SW + t*d, so the x slice is
+// (64 - 1)*SW + 1 + (KT-1)*d positions wide and, in packed mode, an x segment is segp*SW positions.
+template <int KT, int XC, bool PACK = false, int SW = 1>
 __global__ __launch_bounds__(kThreads) void conv1d_dense_grad_weight_kernel(
     const float *__restrict__ x, const float *__restrict__ gy, float *__restrict__ gw, GwGeom gm, int XPITCH,
     int slabs_per_row, int64_t total_slabs, int slabs, int co_blocks, int ci_blocks, int tap_groups)
@@ -263,7 +266,7 @@ __global__ __launch_bounds__(kThreads) void conv1d_dense_grad_weight_kernel(
     const int ka = tg_all / groups_per_krow, tg = tg_all - ka * groups_per_krow;     // my kernel row, my group in it
     const int co0 = cob * 32, ci0 = cib * 32, t0 = tg * KT;
     const int nt = (k - t0 < KT) ? k - t0 : KT;      // live taps of this group
-    const int xw = kPw + (KT - 1) * dilation;        // staged x positions per slab
+    const int xw = (kPw - 1) * SW + 1 + (KT - 1) * dilation;     // staged x positions per slab
     // staging plan: 16 lanes per row of 64 positions (one float4 each), 4 rows per pass;
     // x rows are xw long: XV passes of 16 float4 columns
     const int srow = lane >> 4, scol = 4 * (lane & 15);
@@ -290,7 +293,7 @@ __global__ __launch_bounds__(kThreads) void conv1d_dense_grad_weight_kernel(
     auto prefetch_rows = [&](int64_t slab) {
         const int64_t rho = slab / slabs_per_row;    // (image, output row)
         const int i0 = (int)(slab - rho * slabs_per_row) * kPw;
-        const int j0 = i0 + t0 * dilation - pad;
+        const int j0 = i0 * SW + t0 * dilation - pad;
         const int64_t b = rho / gm.Ho;
         const int ho = (int)(rho - b * gm.Ho);
         const int h = ho * gm.sh - gm.ph + ka;       // the x row this output row meets under kernel row ka
@@ -322,7 +325,8 @@ __global__ __launch_bounds__(kThreads) void conv1d_dense_grad_weight_kernel(
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int q = (c == 0 ? 0 : 64 * (c - 1)) + scol + e;     // c = 0: gy columns; c >= 1: x column block c - 1
-                const int sg = q / gm.segp, o = q - sg * gm.segp;
+                const int sp = c == 0 ? gm.segp : gm.segp * SW;           // positions per segment in this slice
+                const int sg = q / sp, o = q - sg * sp;
                 const int tr = ho0 + sg;
                 const int64_t b = b0 + tr / gm.Ho;
                 const int ho = tr % gm.Ho;
@@ -387,13 +391,13 @@ __global__ __launch_bounds__(kThreads) void conv1d_dense_grad_weight_kernel(
             else prefetch_rows(slab + kWavesPerWg);
         }
         const float *ga = Gl + l32 * kGPitch + half;
-        const float *xb = Xl + l32 * XPITCH + half;
+        const float *xb = Xl + l32 * XPITCH + half * SW;   // my gy position is ip + half
 #pragma unroll 4
         for (int ip = 0; ip < kPw; ip += 2) {
             const float a = ga[ip];
 #pragma unroll
             for (int t = 0; t < KT; ++t) {
-                const float bv = xb[ip + t * dilation];
+                const float bv = xb[ip * SW + t * dilation];
                 acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv, acc[t], 0, 0, 0);
             }
         }
@@ -436,24 +440,24 @@ hipError_t launch_thin_gw(const float *x, const float *gy, float *gw, int B, int
     return hipGetLastError();
 }
 
-template <int KT>
+template <int KT, int SW>
 hipError_t launch_dense_gw(const float *x, const float *gy, float *gw, int64_t B, const GwGeom &gm_in, hipStream_t s,
                            bool *taken)
 {
     GwGeom gm = gm_in;
-    const int xw = kPw + (KT - 1) * gm.dilation;
+    const int xw = (kPw - 1) * SW + 1 + (KT - 1) * gm.dilation;
     const int XPITCH = (xw + 61) / 64 * 64 + 2;      // >= xw, = 2 mod 64
     const size_t stage = (size_t)kWavesPerWg * (32 * kGPitch + 32 * XPITCH) * sizeof(float);
     const size_t red = (size_t)kWavesPerWg * 32 * (32 * KT + 1) * sizeof(float);
     const size_t lds = stage > red ? stage : red;
-    *taken = lds <= 128 * 1024 && xw <= 256;        // above 64 KB the kernel's LDS limit is raised below
+    *taken = lds <= 156 * 1024 && xw <= 256;        // above 64 KB the kernel's LDS limit is raised below
     if (!*taken) return hipSuccess;
     const int slabs_per_row = (gm.Lo + kPw - 1) / kPw;
     // rows of at most half a slab (with their tap margin) are packed several to a slab
-    gm.segp = gm.Lo + (KT - 1) * gm.dilation;
+    gm.segp = gm.Lo + ((KT - 1) * gm.dilation + SW - 1) / SW;
     gm.nseg = kPw / gm.segp;
     gm.rows_total = B * gm.Ho;
-    const bool pack = gm.nseg >= 2 && xw <= 128 && g_opt.conv2d_variant != 3;
+    const bool pack = gm.nseg >= 2 && xw <= 64 * (SW + 1) && g_opt.conv2d_variant != 3;
     const int64_t total_slabs = pack ? (gm.rows_total + gm.nseg - 1) / gm.nseg : B * gm.Ho * slabs_per_row;
     const int co_blocks = (gm.Cout + 31) / 32, ci_blocks = (gm.Cin + 31) / 32;
     const int tap_groups = gm.kh * ((gm.k + KT - 1) / KT);
@@ -472,23 +476,37 @@ hipError_t launch_dense_gw(const float *x, const float *gy, float *gw, int64_t B
 #define SWS_DGW(XC, PACK)                                                                                         \
     case XC:                                                                                                      \
         if (lds > 64 * 1024) {                                                                                    \
-            const hipError_t ea = hipFuncSetAttribute((const void *)conv1d_dense_grad_weight_kernel<KT, XC, PACK>, \
+            const hipError_t ea = hipFuncSetAttribute((const void *)conv1d_dense_grad_weight_kernel<KT, XC, PACK, SW>, \
                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);      \
             if (ea != hipSuccess) return ea;                                                                      \
         }                                                                                                         \
-        hipLaunchKernelGGL((conv1d_dense_grad_weight_kernel<KT, XC, PACK>), dim3((unsigned)grid), dim3(kThreads), lds, \
-                           s, x, gy, gw, gm, XPITCH, slabs_per_row, total_slabs, (int)slabs, co_blocks, ci_blocks, \
-                           tap_groups);                                                                           \
+        hipLaunchKernelGGL((conv1d_dense_grad_weight_kernel<KT, XC, PACK, SW>), dim3((unsigned)grid), dim3(kThreads), \
+                           lds, s, x, gy, gw, gm, XPITCH, slabs_per_row, total_slabs, (int)slabs, co_blocks,      \
+                           ci_blocks, tap_groups);                                                                \
         break
-    if (pack) {
-        switch ((xw + 63) / 64) {
-            SWS_DGW(1, true); SWS_DGW(2, true);
-        default: *taken = false; return hipSuccess;
+    if constexpr (SW == 2) {                         // slices of 127 + (KT-1)*d positions: two or three column blocks
+        if (pack) {
+            switch ((xw + 63) / 64) {
+                SWS_DGW(2, true); SWS_DGW(3, true);
+            default: *taken = false; return hipSuccess;
+            }
+        } else {
+            switch ((xw + 63) / 64) {
+                SWS_DGW(2, false); SWS_DGW(3, false);
+            default: *taken = false; return hipSuccess;
+            }
         }
     } else {
-        switch ((xw + 63) / 64) {
-            SWS_DGW(1, false); SWS_DGW(2, false); SWS_DGW(3, false); SWS_DGW(4, false);
-        default: *taken = false; return hipSuccess;
+        if (pack) {
+            switch ((xw + 63) / 64) {
+                SWS_DGW(1, true); SWS_DGW(2, true);
+            default: *taken = false; return hipSuccess;
+            }
+        } else {
+            switch ((xw + 63) / 64) {
+                SWS_DGW(1, false); SWS_DGW(2, false); SWS_DGW(3, false); SWS_DGW(4, false);
+            default: *taken = false; return hipSuccess;
+            }
         }
     }
 #undef SWS_DGW
@@ -499,10 +517,17 @@ hipError_t launch_dense_gw(const float *x, const float *gy, float *gw, int64_t B
 hipError_t launch_dense_gw_taps(const float *x, const float *gy, float *gw, int64_t B, const GwGeom &gm, hipStream_t s,
                                 bool *taken)
 {
-    if (gm.k == 1) return launch_dense_gw<1>(x, gy, gw, B, gm, s, taken);
-    if (gm.k == 2) return launch_dense_gw<2>(x, gy, gw, B, gm, s, taken);
-    if (gm.k == 3) return launch_dense_gw<3>(x, gy, gw, B, gm, s, taken);
-    return launch_dense_gw<4>(x, gy, gw, B, gm, s, taken);
+    if (gm.sw == 2) {
+        if (gm.k == 1) return launch_dense_gw<1, 2>(x, gy, gw, B, gm, s, taken);
+        if (gm.k == 2) return launch_dense_gw<2, 2>(x, gy, gw, B, gm, s, taken);
+        if (gm.k == 3) return launch_dense_gw<3, 2>(x, gy, gw, B, gm, s, taken);
+        return launch_dense_gw<4, 2>(x, gy, gw, B, gm, s, taken);
+    }
+    if (gm.sw != 1) { *taken = false; return hipSuccess; }
+    if (gm.k == 1) return launch_dense_gw<1, 1>(x, gy, gw, B, gm, s, taken);
+    if (gm.k == 2) return launch_dense_gw<2, 1>(x, gy, gw, B, gm, s, taken);
+    if (gm.k == 3) return launch_dense_gw<3, 1>(x, gy, gw, B, gm, s, taken);
+    return launch_dense_gw<4, 1>(x, gy, gw, B, gm, s, taken);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -518,16 +543,20 @@ __global__ __launch_bounds__(kThreads) void conv2d_grad_input_naive_kernel(
         const int h = (int)((o / W) % H);
         const int ci = (int)((o / ((int64_t)W * H)) % Cin);
         const int64_t n = o / ((int64_t)W * H * Cin);
+        // the taps that reach this cell: a = (h + ph) mod sh, + sh, ... while the output row
+        // (h + ph - a) / sh exists; the same along the row
+        const int a_lo_raw = h + ph - (Ho - 1) * sh, b_lo_raw = c + pw - (Wo - 1) * sw;
+        int a0 = (h + ph) % sh, b0 = (c + pw) % sw;
+        if (a0 < a_lo_raw) a0 += (a_lo_raw - a0 + sh - 1) / sh * sh;
+        if (b0 < b_lo_raw) b0 += (b_lo_raw - b0 + sw - 1) / sw * sw;
+        const int a1 = h + ph < kh - 1 ? h + ph : kh - 1, b1 = c + pw < kw - 1 ? c + pw : kw - 1;
         float acc = 0.0f;
-        for (int a = 0; a < kh; ++a) {
-            const int nh = h + ph - a;
-            if (nh < 0 || nh % sh || nh / sh >= Ho) continue;
-            for (int b = 0; b < kw; ++b) {
-                const int nw = c + pw - b;
-                if (nw < 0 || nw % sw || nw / sw >= Wo) continue;
-                for (int co = 0; co < Cout; ++co)
-                    acc += wgt[(((int64_t)co * Cin + ci) * kh + a) * kw + b] *
-                           gy[((n * Cout + co) * (int64_t)Ho + nh / sh) * Wo + nw / sw];
+        for (int a = a0; a <= a1; a += sh) {
+            const int nh = (h + ph - a) / sh;
+            for (int b = b0; b <= b1; b += sw) {
+                const float *wr = wgt + ((int64_t)ci * kh + a) * kw + b;
+                const float *gr = gy + (n * Cout * (int64_t)Ho + nh) * Wo + (c + pw - b) / sw;
+                for (int co = 0; co < Cout; ++co) acc += wr[(int64_t)co * Cin * kh * kw] * gr[(int64_t)co * Ho * Wo];
             }
         }
         gx[o] = acc;
@@ -592,13 +621,13 @@ hipError_t launch_conv2d_grad_weight(const float *x, const float *gy, float *gw,
 {
     const int64_t n_gw = Cout * Cin * kh * kw;
     if (n_gw > 2147483647LL) return hipErrorInvalidValue;
-    if (N > 0 && sw == 1 && Cin >= 2 && g_opt.conv2d_variant != 1 && H * W <= 2147483647LL && Ho * Wo <= 2147483647LL) {
+    if (N > 0 && sw <= 2 && Cin >= 2 && g_opt.conv2d_variant != 1 && H * W <= 2147483647LL && Ho * Wo <= 2147483647LL) {
         int64_t fg = (n_gw + kThreads - 1) / kThreads;
         if (fg > 4096) fg = 4096;
         hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)fg), dim3(kThreads), 0, s, gw, n_gw);
         GwGeom gm;
         gm.Cin = (int)Cin; gm.Cout = (int)Cout; gm.L = (int)W; gm.Lo = (int)Wo; gm.k = kw; gm.pad = pw; gm.dilation = 1;
-        gm.H = (int)H; gm.Ho = (int)Ho; gm.kh = kh; gm.sh = sh; gm.ph = ph; gm.x_cs = H * W; gm.gy_cs = Ho * Wo;
+        gm.H = (int)H; gm.Ho = (int)Ho; gm.kh = kh; gm.sh = sh; gm.ph = ph; gm.sw = sw; gm.x_cs = H * W; gm.gy_cs = Ho * Wo;
         bool taken = false;
         const hipError_t e = launch_dense_gw_taps(x, gy, gw, N, gm, s, &taken);
         if (taken || e != hipSuccess) return e;
@@ -636,7 +665,7 @@ hipError_t launch_conv1d_grad_weight(const float *x, const float *gy, float *gw,
     const int variant = g_opt.conv1d_variant;        // 1 forces direct evaluation (A/B and tests)
     if (n_gw > 2147483647LL) return hipErrorInvalidValue;
     const bool thin_ok = B > 0 && cig == 1 && stride == 1 && dilation == 1 && k <= 64 && B <= 2147483647LL && variant != 1;
-    const bool dense_ok = B > 0 && groups == 1 && stride == 1 && Cin >= 2 && variant != 1;
+    const bool dense_ok = B > 0 && groups == 1 && stride <= 2 && Cin >= 2 && variant != 1;
     if (thin_ok || dense_ok) {
         int64_t fg = (n_gw + kThreads - 1) / kThreads;
         if (fg > 4096) fg = 4096;
@@ -656,7 +685,7 @@ hipError_t launch_conv1d_grad_weight(const float *x, const float *gy, float *gw,
     if (dense_ok) {
         GwGeom gm;
         gm.Cin = (int)Cin; gm.Cout = (int)Cout; gm.L = (int)L; gm.Lo = (int)Lo; gm.k = k; gm.pad = pad; gm.dilation = dilation;
-        gm.H = 1; gm.Ho = 1; gm.kh = 1; gm.sh = 1; gm.ph = 0; gm.x_cs = L; gm.gy_cs = Lo;
+        gm.H = 1; gm.Ho = 1; gm.kh = 1; gm.sh = 1; gm.ph = 0; gm.sw = stride; gm.x_cs = L; gm.gy_cs = Lo;
         bool taken = false;
         const hipError_t e = launch_dense_gw_taps(x, gy, gw, B, gm, s, &taken);
         if (taken || e != hipSuccess) return e;

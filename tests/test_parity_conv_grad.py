@@ -198,6 +198,25 @@ def test_conv1d_adjoints_short_rows(B, case):
     test_exact_on_small_integers(B, case)
 
 
+# stride 2 along the row on the matrix-core grad-weight kernel (plain and packed slabs)
+STRIDE2_2D = [(2, 16, 28, 28, 24, 3, 3, 2, 2, 1, 1), (2, 32, 30, 30, 16, 1, 1, 2, 2, 0, 0), (2, 3, 40, 40, 16, 7, 7, 2, 2, 3, 3),
+              (6, 8, 9, 13, 8, 3, 3, 2, 2, 1, 1), (1, 8, 12, 300, 8, 3, 3, 1, 2, 1, 1), (3, 8, 20, 33, 12, 2, 4, 3, 2, 0, 1)]
+STRIDE2_1D = [(2, 16, 700, 24, 5, 2, 2, 3, 1), (3, 8, 1001, 8, 3, 2, 1, 1, 1), (20, 8, 25, 8, 3, 2, 1, 1, 1), (2, 40, 300, 33, 1, 2, 0, 1, 1)]
+
+
+@pytest.mark.parametrize("integer", [False, True])
+@pytest.mark.parametrize("case", STRIDE2_2D)
+def test_conv2d_adjoints_row_stride_2(B, case, integer):
+    test_conv2d_adjoints(B, case, integer)
+
+
+@pytest.mark.parametrize("case", STRIDE2_1D)
+def test_conv1d_adjoints_stride_2(B, case):
+    test_grad_weight(B, case)
+    test_grad_input(B, case)
+    test_exact_on_small_integers(B, case)
+
+
 def test_packed_and_unpacked_slabs_agree(B):
     """The dense grad-weight kernel with and without row packing (option conv2d_variant = 3 turns it off)."""
     case = SHORT_ROWS_2D[1]
