@@ -608,6 +608,18 @@ hipError_t launch_conv2d_grad_input(const float *gy, const float *wgt, float *gx
                                                 kw - 1 - pw, 1, 1, s, &taken, 1);
         if (taken || e != hipSuccess) return e;
     }
+    if ((sh > 1 || sw > 1) && N > 0 && g_opt.conv2d_variant != 1) {
+        if (kh < sh || kw < sw) {                     // some phases of gx are reached by no tap
+            const int64_t n_gx = N * Cin * H * W;
+            int64_t fg = (n_gx + kThreads - 1) / kThreads;
+            if (fg > 65536) fg = 65536;
+            hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)fg), dim3(kThreads), 0, s, gx, n_gx);
+        }
+        bool taken = false;
+        const hipError_t e = launch_conv2d_grad_input_phases(gy, wgt, gx, N, Cin, H, W, Cout, Ho, Wo, kh, kw, sh, sw, ph,
+                                                             pw, s, &taken);
+        if (taken || e != hipSuccess) return e;
+    }
     int64_t grid = (N * Cin * H * W + kThreads - 1) / kThreads;
     if (grid > 1048576) grid = 1048576;
     hipLaunchKernelGGL(conv2d_grad_input_naive_kernel, dim3((unsigned)grid), dim3(kThreads), 0, s, gy, wgt, gx, N,
@@ -647,6 +659,19 @@ hipError_t launch_conv1d_grad_input(const float *gy, const float *wgt, float *gx
         bool taken = false;
         const hipError_t e = launch_conv1d(gy, wgt, gx, B, Cout, Lo, Cin, L, k, 1, (int32_t)back_pad, dilation, groups, s,
                                            1, &taken);
+        if (taken || e != hipSuccess) return e;
+    }
+    if (stride > 1 && dilation == 1 && groups == 1 && Cin >= 2 && B > 0 && g_opt.conv1d_variant != 1) {
+        // dense channels: the phases of the strided adjoint on the matrix-core kernel (rows of height 1)
+        if (k < stride) {
+            const int64_t n_gx = B * Cin * L;
+            int64_t fg = (n_gx + kThreads - 1) / kThreads;
+            if (fg > 65536) fg = 65536;
+            hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)fg), dim3(kThreads), 0, s, gx, n_gx);
+        }
+        bool taken = false;
+        const hipError_t e = launch_conv2d_grad_input_phases(gy, wgt, gx, B, Cin, 1, L, Cout, 1, Lo, 1, k, 1, stride, 0, pad,
+                                                             s, &taken);
         if (taken || e != hipSuccess) return e;
     }
     int64_t grid = (B * Cin * L + kThreads - 1) / kThreads;

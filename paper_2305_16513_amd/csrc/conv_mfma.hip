@@ -47,6 +47,11 @@ struct ConvGeom {
     int Wt, NRows, CP;                                // staged row pitch, staged rows, channel pitch in LDS
     int CH;                                           // 64-column chunks per staged row
     int tiles_per_img, tiles_c, co_blocks;
+    // (read by the general instance only; kept behind the fields every instance reads)
+    int wlast, wrs, wcs;                              // adjoint view: index of the tap read first, and the steps (in taps of the
+                                                      //   stored kernel) from one row / one tap of this launch's kernel to the next
+    int yH, yW, ysh, ysw, yh0, yw0;                   // general instance: output (oh, ow) is stored at row yh0 + oh*ysh, column
+                                                      //   yw0 + ow*ysw of planes of yH x yW (a phase of a strided adjoint)
 };
 
 // x / d for 0 <= x < 2^20 and 1 <= d < 2^12, exact, a handful of VALU ops instead of the
@@ -358,10 +363,20 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
     constexpr bool TAIL = GEN;
     const bool adj = GEN && g.wadj;
     const int64_t w_sci = adj ? (int64_t)g.Cout * g.wstride : g.wstride;
-    const int w_st = GEN ? (w_ok ? (adj ? -1 : 1) : 0) : 1;   // threads without a pair re-read element 0
-    const float *wsrc = wgt + (w_ok ? (adj ? (int64_t)w_ci * w_sci + (int64_t)(co0 + w_co) * g.wstride + g.wstride - 1 - g.wofs
+    const float *wsrc = wgt + (w_ok ? (adj ? (int64_t)w_ci * w_sci + (int64_t)(co0 + w_co) * g.wstride + g.wlast
                                            : ((int64_t)(co0 + w_co) * g.Cin + w_ci) * g.wstride + g.wofs)
                                     : 0);
+    // general instance: tap t of this launch's kernel sits toff[t] elements from wsrc (plain view:
+    // t; adjoint view: towards the front, by wrs per kernel row and wcs per tap)
+    int toff[KTMAX];
+    if constexpr (GEN) {
+        int ta = 0, tb = 0;
+#pragma unroll
+        for (int t = 0; t < KTMAX; ++t) {
+            toff[t] = t < KT ? (adj ? -(ta * g.wrs + tb * g.wcs) : t) : 0;
+            if (++tb == g.kw) { tb = 0; ++ta; }
+        }
+    }
     float *wdst = Wl + w_co * XP + w_ci;
 
     float xreg[NB][XS], wreg[NB][KTMAX];
@@ -380,9 +395,8 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
             if constexpr (GEN) {
                 const bool wk = w_ok && cb + w_ci < g.Cin;
                 const float *w = wk ? wsrc + cb * w_sci : wgt;
-                const int st = wk ? w_st : 0;
 #pragma unroll
-                for (int t = 0; t < KTMAX; ++t) wreg[nb][t] = w[(t < KT ? t : 0) * st];
+                for (int t = 0; t < KTMAX; ++t) wreg[nb][t] = w[wk ? toff[t] : 0];
             } else {
                 const float *w = wsrc + (w_ok ? cb * g.wstride : 0);
 #pragma unroll
@@ -443,6 +457,19 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
     }
 
     if (!pok) return;
+    if constexpr (GEN) {
+        float *yn = y + n * g.Cout * (int64_t)g.yH * g.yW;
+        const int64_t at = (int64_t)(g.yh0 + oh * g.ysh) * g.yW + g.yw0 + ow * g.ysw;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int co = co0 + wm * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+            if (co < g.Cout) {
+                float *dst = yn + (int64_t)co * g.yH * g.yW + at;
+                *dst = g.accum ? *dst + acc[v] : acc[v];
+            }
+        }
+        return;
+    }
     float *yn = y + n * g.Cout * (int64_t)g.Ho * g.Wo;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
@@ -622,6 +649,8 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
     g.Cin = (int)Cin; g.H = (int)H; g.W = (int)W; g.Cout = (int)Cout; g.Ho = (int)Ho; g.Wo = (int)Wo;
     g.kh = kh; g.kw = kw; g.ph = ph; g.pw = pw; g.sh = sh; g.sw = sw; g.dh = dh; g.dw = dw;
     g.wstride = KT; g.wofs = 0; g.accum = 0; g.wadj = wadj;
+    g.wlast = KT - 1; g.wrs = kw; g.wcs = 1;
+    g.yH = (int)Ho; g.yW = (int)Wo; g.ysh = 1; g.ysw = 1; g.yh0 = 0; g.yw0 = 0;
     // Up to 36 adjacent taps at stride 1 the scalar-read kernel does the whole kernel in one pass,
     // which beats a chain of five or more launches (5 x 5 on [32,64,56,56]: 0.27 ms against 0.41 ms).
     const bool one_pass = !wadj && plain && KT > 9 && KT <= 36 && Cin % 4 == 0 && g_opt.conv2d_variant != 6;
@@ -646,6 +675,7 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
                 L[c].g.kh = na; L[c].g.ph = ph - a0 * dh;
                 L[c].g.kw = nb; L[c].g.pw = pw - b0 * dw;
                 L[c].g.wofs = a0 * kw + b0;           // a chunk of several rows takes whole rows: its taps stay contiguous
+                L[c].g.wlast = KT - 1 - (a0 * kw + b0);
                 L[c].g.accum = c > 0;
                 ok = c8_prepare(&L[c], N);
             }
@@ -674,6 +704,69 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
     // 8 wavefronts, one 32x32 accumulator block each: short workgroups, four waves per SIMD
     if (CIB == 16) return launch<8, 1, 1, 16>(x, wgt, y, g, units, lds, s);
     return launch<8, 1, 1, 4>(x, wgt, y, g, units, lds, s);
+}
+
+// The adjoint of a strided convolution with respect to its input, one output phase at a time.
+// Cells (h, c) of gx with (h + ph) mod sh = rh and (c + pw) mod sw = rc are reached only by the
+// taps a = rh, rh + sh, ..., b = rc, rc + sw, ...; over such a phase the adjoint is a stride-1
+// convolution of gy with that sub-kernel (flipped, channels swapped: the adjoint weight view with a
+// step of sh*kw / sw stored taps per row / tap), written to every sh-th row and sw-th column of gx.
+// Sub-kernels of more than 9 taps run as chains of launches like any other kernel.  A phase no tap
+// reaches (kernel smaller than the stride) is cleared by the caller.  *taken = false: nothing was
+// launched.
+hipError_t launch_conv2d_grad_input_phases(const float *gy, const float *wgt, float *gx, int64_t N, int64_t Cin,
+                                           int64_t H, int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh,
+                                           int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw, hipStream_t s,
+                                           bool *taken)
+{
+    *taken = false;
+    const int KTF = kh * kw;
+    if (H * W > 2147483647LL / 2 || Cout * Cin * KTF > 2147483647LL / 2 || sh * sw > 16) return hipSuccess;
+    constexpr int kMaxLaunch = 64;
+    C8Launch L[kMaxLaunch];
+    int n_launch = 0;
+    for (int rh = 0; rh < sh; ++rh)
+        for (int rc = 0; rc < sw; ++rc) {
+            const int KA = rh < kh ? (kh - rh + sh - 1) / sh : 0, KB = rc < kw ? (kw - rc + sw - 1) / sw : 0;
+            if (KA == 0 || KB == 0) continue;         // no tap reaches this phase
+            // first cell of the phase and the index i0 of its row among "h = sh*i + rh - ph"
+            const int i0 = ph > rh ? (ph - rh + sh - 1) / sh : 0, j0 = pw > rc ? (pw - rc + sw - 1) / sw : 0;
+            const int h0 = sh * i0 + rh - ph, c0 = sw * j0 + rc - pw;
+            if (h0 >= H || c0 >= W) continue;         // no cell of the plane is in this phase
+            const int nH = (int)((H - h0 + sh - 1) / sh), nW = (int)((W - c0 + sw - 1) / sw);
+            ConvGeom g;
+            g.Cin = (int)Cout; g.H = (int)Ho; g.W = (int)Wo; g.Cout = (int)Cin; g.Ho = nH; g.Wo = nW;
+            g.sh = 1; g.sw = 1; g.dh = 1; g.dw = 1;
+            g.wstride = KTF; g.wofs = 0; g.wadj = 1;
+            g.wrs = sh * kw; g.wcs = sw;
+            g.yH = (int)H; g.yW = (int)W; g.ysh = sh; g.ysw = sw; g.yh0 = h0; g.yw0 = c0;
+            const int last = (rh + sh * (KA - 1)) * kw + rc + sw * (KB - 1);     // the sub-kernel's last tap, read first
+            // out[i][j] = sum_{u,v} K[u][v] * gy[i + i0 - (KA-1) + u][j + j0 - (KB-1) + v]: padding KA-1-i0, KB-1-j0
+            const int PA = KA - 1 - i0, PB = KB - 1 - j0;
+            const int KT = KA * KB;
+            const int rows_per = KT <= 9 ? KA : (KB <= 9 ? 9 / KB : 1);
+            const int taps_per = KB <= 9 ? KB : 9;
+            const int row_chunks = (KA + rows_per - 1) / rows_per, run_chunks = (KB + taps_per - 1) / taps_per;
+            for (int c = 0; c < row_chunks * run_chunks; ++c) {
+                if (n_launch == kMaxLaunch) return hipSuccess;
+                const int a0 = (c / run_chunks) * rows_per, b0 = (c % run_chunks) * taps_per;
+                const int na = KA - a0 < rows_per ? KA - a0 : rows_per, nb = KB - b0 < taps_per ? KB - b0 : taps_per;
+                C8Launch &Lc = L[n_launch];
+                Lc.g = g;
+                Lc.g.kh = na; Lc.g.ph = PA - a0;
+                Lc.g.kw = nb; Lc.g.pw = PB - b0;
+                Lc.g.wlast = last - (a0 * g.wrs + b0 * g.wcs);
+                Lc.g.accum = c > 0;
+                if (!c8_prepare(&Lc, N)) return hipSuccess;
+                ++n_launch;
+            }
+        }
+    *taken = true;
+    for (int c = 0; c < n_launch; ++c) {
+        const hipError_t e = c8_launch(L[c], gy, wgt, gx, s);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace sws

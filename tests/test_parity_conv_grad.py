@@ -217,6 +217,21 @@ def test_conv1d_adjoints_stride_2(B, case):
     test_exact_on_small_integers(B, case)
 
 
+def test_strided_grad_input_by_phases_agrees_with_direct_evaluation(B):
+    """Small-integer data: the phase-wise matrix-core route and the direct kernel must give the same bits."""
+    for case in (STRIDE2_2D[0], STRIDE2_2D[2], STRIDE2_2D[5], (2, 8, 21, 22, 8, 2, 2, 3, 4, 1, 0)):
+        n, cin, h, wd, cout, kh, kw, sh, sw, ph, pw = case
+        x, w, g = _data2d(case, 91, integer=True)
+        fast = to_host(B.sws_conv2d_grad_input(to_gpu(g), to_gpu(w), h, wd, sh, sw, ph, pw))
+        B.sws_set_option("conv2d_variant", 1)
+        try:
+            direct = to_host(B.sws_conv2d_grad_input(to_gpu(g), to_gpu(w), h, wd, sh, sw, ph, pw))
+        finally:
+            B.sws_set_option("conv2d_variant", 0)
+        assert np.array_equal(fast, direct), str(case)
+        assert np.array_equal(fast.astype(np.float64), oracle.conv2d_grad_input(g, w, h, wd, sh, sw, ph, pw)[0]), str(case)
+
+
 def test_packed_and_unpacked_slabs_agree(B):
     """The dense grad-weight kernel with and without row packing (option conv2d_variant = 3 turns it off)."""
     case = SHORT_ROWS_2D[1]

@@ -283,3 +283,23 @@ def test_conv2d_grad_weight_short_rows_random(B, seed):
     gw = to_host(B.sws_conv2d_grad_weight(to_gpu(x), to_gpu(g), kh, kw, sh, 1, ph, pw))
     rw, mw = oracle.conv2d_grad_weight(x, g, kh, kw, sh, 1, ph, pw)
     assert_within_tol(gw, rw, mw, "seed %d: N %d Cin %d H %d W %d Cout %d k %dx%d sh %d p %dx%d" % (seed, n, cin, h, wd, cout, kh, kw, sh, ph, pw))
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_conv2d_grad_input_strided_random(B, seed):
+    """Strides up to 4 (also above the kernel size: cells no tap reaches must come out zero), kernels
+    up to 7 x 7 (phases of more than 9 taps run as chains), paddings up to k - 1."""
+    r = _rng(8100 + seed)
+    cin, cout = int(r.integers(1, 40)), int(r.integers(1, 40))
+    kh, kw = int(r.integers(1, 8)), int(r.integers(1, 8))
+    sh, sw = int(r.integers(1, 5)), int(r.integers(1, 5))
+    ph, pw = int(r.integers(0, kh)), int(r.integers(0, kw))
+    h = max(1, kh - 2 * ph) + int(r.integers(0, 40))
+    wd = max(1, kw - 2 * pw) + int(r.integers(0, 60 if seed % 5 else 260))
+    n = int(r.integers(1, 4))
+    ho, wo = (h + 2 * ph - kh) // sh + 1, (wd + 2 * pw - kw) // sw + 1
+    w = (r.standard_normal((cout, cin, kh, kw), dtype=np.float32) * np.float32(0.2)).astype(np.float32)
+    g = r.standard_normal((n, cout, ho, wo), dtype=np.float32)
+    gx = to_host(B.sws_conv2d_grad_input(to_gpu(g), to_gpu(w), h, wd, sh, sw, ph, pw))
+    rx, mx = oracle.conv2d_grad_input(g, w, h, wd, sh, sw, ph, pw)
+    assert_within_tol(gx, rx, mx, "seed %d: N %d Cin %d H %d W %d Cout %d k %dx%d s %dx%d p %dx%d" % (seed, n, cin, h, wd, cout, kh, kw, sh, sw, ph, pw))
