@@ -343,6 +343,24 @@ def sweeps_table(torch, B, workloads, iters=20):
                                  "frac_fp32_mfma_peak": round(fl / ms / 1e9 / 157.3, 4)}
     del xr, gr, gxr
     torch.cuda.empty_cache()
+    # a down-sampling layer (3 x 3, stride 2, 128 -> 128 channels on 56 x 56 planes) and a late layer with short
+    # rows (3 x 3, 256 -> 256 channels on 14 x 14 planes), 32 images: forward and both adjoints
+    for tag, ch, hh, st in (("s2_3x3_128ch_56x56", 128, 56, 2), ("s1_3x3_256ch_14x14", 256, 14, 1)):
+        ho = (hh + 2 - 3) // st + 1
+        xs = torch.empty(32, ch, hh, hh, device="cuda").normal_()
+        ws = torch.empty(ch, ch, 3, 3, device="cuda").normal_(0, 0.03)
+        ys = torch.empty(32, ch, ho, ho, device="cuda")
+        gs = torch.empty(32, ch, ho, ho, device="cuda").normal_()
+        gxs, gws = torch.empty_like(xs), torch.empty_like(ws)
+        fl = 2.0 * 32 * ch * ch * 9 * ho * ho
+        for name, fn in (("forward", lambda: B.sws_conv2d(xs, ws, st, st, 1, 1, y=ys)),
+                         ("grad_input", lambda: B.sws_conv2d_grad_input(gs, ws, hh, hh, st, st, 1, 1, gx=gxs)),
+                         ("grad_weight", lambda: B.sws_conv2d_grad_weight(xs, gs, 3, 3, st, st, 1, 1, gw=gws))):
+            ms = time_launches(torch, fn, iters)
+            out["adjoints"]["layer_%s_%s" % (tag, name)] = {"us": round(ms * 1e3, 2), "TFLOPs": round(fl / ms / 1e9, 2),
+                                                             "frac_fp32_mfma_peak": round(fl / ms / 1e9 / 157.3, 4)}
+        del xs, ws, ys, gs, gxs, gws
+    torch.cuda.empty_cache()
     return out
 
 
@@ -416,6 +434,18 @@ def run_only(torch, B, workloads, name, steps):
         y = torch.empty(16, 64, 4094, device="cuda")
         op = 1 if "max" in name else 0
         fn = lambda: B.sws_slide1d(op, x2, 3, 1 / 3, y=y)
+    elif name.startswith("layer_"):                       # layer_<s2_3x3_128ch_56x56|s1_3x3_256ch_14x14>_<forward|grad_input|grad_weight>
+        tag, what = (name[6:].rsplit("_", 2)[0], "_".join(name.rsplit("_", 2)[1:])) if name.endswith(("grad_input", "grad_weight")) else (name[6:].rsplit("_", 1)[0], "forward")
+        ch, hh, st = {"s2_3x3_128ch_56x56": (128, 56, 2), "s1_3x3_256ch_14x14": (256, 14, 1)}[tag]
+        ho = (hh + 2 - 3) // st + 1
+        xs = torch.empty(32, ch, hh, hh, device="cuda").normal_()
+        ws = torch.empty(ch, ch, 3, 3, device="cuda").normal_(0, 0.03)
+        ys = torch.empty(32, ch, ho, ho, device="cuda")
+        gs = torch.empty(32, ch, ho, ho, device="cuda").normal_()
+        gxs, gws = torch.empty_like(xs), torch.empty_like(ws)
+        fn = {"forward": lambda: B.sws_conv2d(xs, ws, st, st, 1, 1, y=ys),
+              "grad_input": lambda: B.sws_conv2d_grad_input(gs, ws, hh, hh, st, st, 1, 1, gx=gxs),
+              "grad_weight": lambda: B.sws_conv2d_grad_weight(xs, gs, 3, 3, st, st, 1, 1, gw=gws)}[what]
     elif name in ("grad_cfg3_maxpool_s1", "grad_cfg3_maxpool_s2"):
         x3 = g(workloads.make(3)[0])
         s = int(name[-1])
