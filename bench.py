@@ -91,21 +91,24 @@ def ops_table(torch, B, workloads, iters=20):
         def pick():
             state["i"] = (state["i"] + 1) % n
             return sets[state["i"]]
-        return sets[0], pick
+        return sets[0], pick, sets
 
-    def graph_ms(launch, args, n=20, replays=5):
+    def graph_ms(launch, args, n=20, replays=5, sets=None):
         """Mean duration of one launch inside a HIP graph of n back-to-back launches: what the
-        small operators cost once the host's launch path (about 10 us from Python) is out of the way."""
+        small operators cost once the host's launch path (about 10 us from Python) is out of the way.
+        With `sets` the launches of the graph go round the rotating buffer sets (the cold figure)."""
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
             launch(*args)
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
+        if sets is not None:
+            n = len(sets) * max(1, (n + len(sets) - 1) // len(sets))
         gr = torch.cuda.CUDAGraph()
         with torch.cuda.graph(gr):
-            for _ in range(n):
-                launch(*args)
+            for i in range(n):
+                launch(*(sets[i % len(sets)] if sets is not None else args))
         gr.replay()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -117,7 +120,7 @@ def ops_table(torch, B, workloads, iters=20):
         return e0.elapsed_time(e1) / (n * replays)
 
     def record(name, launch, make_args, nbytes, flops=0.0, graph=False):
-        first, pick = rotate(make_args, nbytes)
+        first, pick, sets = rotate(make_args, nbytes)
         warm = time_launches(torch, lambda: launch(*first), iters)
         cold = time_launches(torch, lambda: launch(*pick()), iters)
         rec = {"ms_warm": round(warm, 5), "ms_cold": round(cold, 5),
@@ -130,6 +133,10 @@ def ops_table(torch, B, workloads, iters=20):
         if graph:
             rec["ms_in_graph"] = round(graph_ms(launch, first), 5)
             rec["GBps_in_graph"] = round(nbytes / rec["ms_in_graph"] / 1e6, 1)
+            if len(sets) > 1:                          # cold and in a graph: rotating buffers, no host launch path
+                rec["ms_cold_in_graph"] = round(graph_ms(launch, first, sets=sets), 5)
+                rec["GBps_cold_in_graph"] = round(nbytes / rec["ms_cold_in_graph"] / 1e6, 1)
+                rec["frac_hbm_cold_in_graph"] = round(nbytes / rec["ms_cold_in_graph"] / 1e6 / HBM_PEAK_GBPS, 4)
             if flops:
                 rec["GFLOPs_in_graph"] = round(flops / rec["ms_in_graph"] / 1e6, 1)
         out[name] = rec
@@ -162,6 +169,9 @@ def ops_table(torch, B, workloads, iters=20):
         nb = 4 * (2048 * 112 * 112 + 2048 * ho * ho)
         record("cfg3_maxpool3x3_s%d" % s, lambda x, y: B.sws_pool2d(1, x, 3, 3, s, s, 1, 1, 1.0, y=y), mk, nb, graph=True)
         record("cfg3_avgpool3x3_s%d" % s, lambda x, y: B.sws_pool2d(0, x, 3, 3, s, s, 1, 1, 1 / 9, y=y), mk, nb, graph=True)
+    # the ceiling for an operator of this size: a plain copy of the same tensor, timed the same ways
+    mk = lambda: (x3.clone(), torch.empty(32, 64, 112, 112, device="cuda"))
+    record("cfg3_sized_copy", lambda x, y: B.sws_copy(x, y), mk, 2 * 4 * 2048 * 112 * 112, graph=True)
     del x3
     # cfg4: conv2d [32,64,56,56] x [64,64,3,3], pad 1
     x4, w4 = workloads.make(4)
