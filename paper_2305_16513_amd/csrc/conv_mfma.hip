@@ -566,8 +566,9 @@ bool c8_prepare(C8Launch *L, int64_t N)
     const size_t lds1 = 4 * ((size_t)xfloats + (size_t)KT * kCoTile * 12);
     // few taps: four channel blocks per barrier pair, if they fit
     const bool general = g.Cin % 8 != 0 || g.wadj;    // the general instance stages one channel block per barrier pair
-    const bool nb4 = !general && KT == 3 && g.kw == 3 && g.Cin % 32 == 0 && 8 * g.NRows * g.CH <= 32 && 4 * lds1 <= 64 * 1024 &&
-                     g_opt.conv2d_variant != 5;
+    // (the general instance has it for 1 x 1 kernels only: the adjoint of a 1 x 1 convolution)
+    const bool nb4 = ((!general && KT == 3 && g.kw == 3) || KT == 1) && g.Cin % 32 == 0 && 8 * g.NRows * g.CH <= 32 &&
+                     4 * lds1 <= 64 * 1024 && g_opt.conv2d_variant != 5;
     const bool seg128 = 8 * g.NRows * g.CH > 64;          // only reached with 8 wavefronts (strided: tall tiles)
     g.CP = xfloats;
     for (int i = 0; i < 128; ++i) {
@@ -578,7 +579,7 @@ bool c8_prepare(C8Launch *L, int64_t N)
     L->lds = (nb4 ? 4 : 1) * lds1;
     L->waves = seg128 ? 8 : best_w;
     L->tail = general;
-    L->ktt = (KT == 9 && g.kw == 3) ? 9 : ((KT == 3 && g.kw == 3) ? 3 : 0);
+    L->ktt = (KT == 9 && g.kw == 3) ? 9 : ((KT == 3 && g.kw == 3) ? 3 : ((KT == 1 && nb4 && !seg128) ? 1 : 0));
     L->nb = (nb4 && !seg128) ? 4 : 1;
     L->seg = seg128 ? 128 : (L->nb == 4 ? 32 : 64);
     return true;
@@ -606,7 +607,15 @@ hipError_t c8_launch(const C8Launch &L, const float *x, const float *wgt, float 
         case 12: SWS_C8T(KTT, 12, 64); break;                                                                   \
         default: SWS_C8T(KTT, 14, 64); break;                                                                   \
     }
-        if (L.ktt == 9) { SWS_C8T_W(9) }
+        if (L.nb == 4) {                              // 1 x 1 through the adjoint view, four channel blocks per barrier pair
+            switch (L.waves) {
+            case 8: hipLaunchKernelGGL((conv2d_mfma_c8_kernel<1, 8, 4, 32, true>), L.grid, dim3(8 * 64), L.lds, s, x, wgt, y, L.g, L.sp); break;
+            case 10: hipLaunchKernelGGL((conv2d_mfma_c8_kernel<1, 10, 4, 32, true>), L.grid, dim3(10 * 64), L.lds, s, x, wgt, y, L.g, L.sp); break;
+            case 12: hipLaunchKernelGGL((conv2d_mfma_c8_kernel<1, 12, 4, 32, true>), L.grid, dim3(12 * 64), L.lds, s, x, wgt, y, L.g, L.sp); break;
+            default: hipLaunchKernelGGL((conv2d_mfma_c8_kernel<1, 14, 4, 32, true>), L.grid, dim3(14 * 64), L.lds, s, x, wgt, y, L.g, L.sp); break;
+            }
+        }
+        else if (L.ktt == 9) { SWS_C8T_W(9) }
         else if (L.ktt == 3) { SWS_C8T_W(3) }
         else { SWS_C8T_W(0) }
 #undef SWS_C8T_W
@@ -617,6 +626,8 @@ hipError_t c8_launch(const C8Launch &L, const float *x, const float *wgt, float 
         else SWS_C8(0, 8, 1, 128);
     } else if (L.ktt == 9) {
         SWS_C8_W(9, 1, 64)
+    } else if (L.nb == 4 && L.ktt == 1) {             // 1 x 1: four channel blocks per barrier pair
+        SWS_C8_W(1, 4, 32)
     } else if (L.nb == 4) {
         SWS_C8_W(3, 4, 32)
     } else if (L.ktt == 3) {
@@ -645,6 +656,12 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
     const bool plain = sh == 1 && sw == 1 && dh == 1 && dw == 1;
     const int KT = kh * kw;
     if (Ho * Wo > 2147483647LL / 2 || Cout * Cin * KT > 2147483647LL / 2) return hipSuccess;
+    // A 1 x 1 kernel without stride or padding does not see the rows: the plane is one long row, cut
+    // into column tiles (narrow planes would otherwise stage half-empty 64-column segments).
+    if (KT == 1 && plain && ph == 0 && pw == 0 && H > 1) {
+        W *= H; H = 1;
+        Wo *= Ho; Ho = 1;
+    }
     ConvGeom g;
     g.Cin = (int)Cin; g.H = (int)H; g.W = (int)W; g.Cout = (int)Cout; g.Ho = (int)Ho; g.Wo = (int)Wo;
     g.kh = kh; g.kw = kw; g.ph = ph; g.pw = pw; g.sh = sh; g.sw = sw; g.dh = dh; g.dw = dw;
