@@ -19,6 +19,7 @@ from .ref import (  # noqa: F401
     conv2d,
     conv2d_grad_input,
     conv2d_grad_weight,
+    avgpool2d_grad,
     maxpool2d_grad,
     pool2d,
     pool2d_ex,

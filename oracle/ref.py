@@ -59,6 +59,9 @@ def _load():
         for f in (lib.sws_ref_conv2d_grad_input, lib.sws_ref_conv2d_grad_weight):
             f.restype = ctypes.c_int
             f.argtypes = [_fp, _fp, _dp, _dp, _i64, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _i32]
+        lib.sws_ref_avgpool2d_grad.restype = ctypes.c_int
+        lib.sws_ref_avgpool2d_grad.argtypes = [_fp, _dp, _dp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _i32,
+                                               ctypes.c_int, ctypes.c_double]
         lib.sws_ref_maxpool2d_grad.restype = ctypes.c_int
         lib.sws_ref_maxpool2d_grad.argtypes = [_fp, _fp, _dp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _i32]
         lib.sws_ref_round16.restype = ctypes.c_int
@@ -309,6 +312,22 @@ def conv2d_grad_weight(x, gy, kh, kw, sh=1, sw=1, ph=0, pw=0):
     if rc:
         raise ValueError("sws_ref_conv2d_grad_weight rejected its arguments")
     return gw, s
+
+
+def avgpool2d_grad(gy, h, wd, kh, kw, sh=1, sw=1, ph=0, pw=0, div_valid=False, scale=1.0):
+    """gy: [N, C, Ho, Wo] float32, (h, wd) = the pooled plane -> (gx, abs_sum) [N, C, H, W] float64: the
+    adjoint of pool2d_ex(ADD, pads = (ph, pw, ph, pw), div_valid, scale)."""
+    gy = _f32(gy)
+    n, c, ho, wo = gy.shape
+    if ho != (h + 2 * ph - kh) // sh + 1 or wo != (wd + 2 * pw - kw) // sw + 1:
+        raise ValueError("gy does not have the pooled shape")
+    gx = np.empty((n, c, h, wd), np.float64)
+    s = np.empty((n, c, h, wd), np.float64)
+    rc = _load().sws_ref_avgpool2d_grad(_ptr_f(gy), _ptr_d(gx), _ptr_d(s), n, c, h, wd, kh, kw, sh, sw, ph, pw,
+                                        1 if div_valid else 0, float(scale))
+    if rc:
+        raise ValueError("sws_ref_avgpool2d_grad rejected its arguments")
+    return gx, s
 
 
 def maxpool2d_grad(x, gy, kh, kw, sh=1, sw=1, ph=0, pw=0):

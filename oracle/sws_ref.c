@@ -25,6 +25,9 @@
  *   sws_ref_maxpool2d_grad  the adjoint of max pooling at a point x (Section 2.3's max operator,
  *                    training side): every window sends its output gradient to the cell that
  *                    holds its maximum — the first such cell in row-major order when several tie.
+ *   sws_ref_avgpool2d_grad  the adjoint of sws_ref_pool2d_ex for ADD with symmetric padding: every
+ *                    window sends f * gy to each of its cells inside the plane, f = scale or
+ *                    scale / (number of such cells) — the forward sum's terms, scattered.
  *   sws_ref_slide1d_padded  Eq. 3 on rows extended at both ends (the boundary conditions
  *                    named in Section 3: padding, mirroring, periodicity; plus edge
  *                    replication).  Every window element's index is mapped back into
@@ -566,6 +569,52 @@ int sws_ref_maxpool2d_grad(const float *x, const float *gy, double *gx, int64_t 
                         if (best < 0 || xp[h * W + c] > xp[best]) best = h * W + c;
                     }
                 gp[best] += (double)gy[(p * Ho + ho) * Wo + wo];
+            }
+    }
+    return 0;
+}
+
+/* The adjoint of average pooling (sws_ref_pool2d_ex, ADD, padding ph / pw on both sides): with
+ * loss = sum(gy * y) and y = f * sum of the window's cells inside the plane, every such cell
+ * receives f * gy of every window that holds it; f = scale (div_valid = 0) or scale / n with n
+ * the number of cells of that window inside the plane.  Scatter form, windows in row-major order.
+ * gx, abs_sum (optional): N*C*H*W doubles, overwritten. */
+int sws_ref_avgpool2d_grad(const float *gy, double *gx, double *abs_sum, int64_t N, int64_t C, int64_t H, int64_t W,
+                           int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw, int div_valid,
+                           double scale)
+{
+    if (N < 0 || C < 0 || H < 1 || W < 1) return 1;
+    if (kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0) return 1;
+    if (ph >= kh || pw >= kw) return 1;
+    if (kh > H + 2 * (int64_t)ph || kw > W + 2 * (int64_t)pw) return 1;
+    const int64_t Ho = (H + 2 * (int64_t)ph - kh) / sh + 1;
+    const int64_t Wo = (W + 2 * (int64_t)pw - kw) / sw + 1;
+    const int64_t planes = N * C;
+    if (planes > 0 && (!gy || !gx)) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t p = 0; p < planes; ++p) {
+        double *gp = gx + p * H * W;
+        double *mp = abs_sum ? abs_sum + p * H * W : 0;
+        for (int64_t e = 0; e < H * W; ++e) {
+            gp[e] = 0.0;
+            if (mp) mp[e] = 0.0;
+        }
+        for (int64_t ho = 0; ho < Ho; ++ho)
+            for (int64_t wo = 0; wo < Wo; ++wo) {
+                int64_t n = 0;
+                for (int32_t a = 0; a < kh; ++a)
+                    for (int32_t b = 0; b < kw; ++b) {
+                        const int64_t h = ho * sh - ph + a, c = wo * sw - pw + b;
+                        if (h >= 0 && h < H && c >= 0 && c < W) ++n;
+                    }
+                const double term = (div_valid ? scale / (double)n : scale) * (double)gy[(p * Ho + ho) * Wo + wo];
+                for (int32_t a = 0; a < kh; ++a)
+                    for (int32_t b = 0; b < kw; ++b) {
+                        const int64_t h = ho * sh - ph + a, c = wo * sw - pw + b;
+                        if (h < 0 || h >= H || c < 0 || c >= W) continue;
+                        gp[h * W + c] += term;
+                        if (mp) mp[h * W + c] += fabs(term);
+                    }
             }
     }
     return 0;

@@ -948,3 +948,50 @@ def test_maxpool2d_grad_is_the_derivative_of_the_pooled_loss(geom):
         assert (loss(xp) - loss(xm)) / 0.5 == gx[idx]
     assert gx.sum() == float(gy.astype(np.float64).sum())
     assert np.array_equal(gx.sum(axis=(2, 3)), gy.astype(np.float64).sum(axis=(2, 3)))
+
+
+# ----------------------------------------------------------------------------- P17
+# The adjoint of average pooling: every window spreads f * gy over its cells inside the plane.
+def test_avgpool2d_grad_hand_written_cases():
+    gy = np.array([[[[1, 10], [100, 1000]]]], np.float32)                  # 2 x 2 windows, stride 1, on a 3 x 3 plane
+    gx, mag = oracle.avgpool2d_grad(gy, 3, 3, 2, 2, scale=0.25)
+    # cell (h, c) collects the windows (ho, wo) with ho in {h-1, h}, wo in {c-1, c} that exist
+    want = np.array([[1, 11, 10], [101, 1111, 1010], [100, 1100, 1000]], np.float64) * 0.25
+    assert np.array_equal(gx[0, 0], want) and np.array_equal(mag[0, 0], want)
+    # stride 2 with padding 1 on a 3 x 3 plane, 3 x 3 windows: windows at rows / cols {-1..1} and {1..3};
+    # window (0,0) holds the 4 real cells (0..1, 0..1), (0,1) the cells (0..1, 1..2), and so on
+    gx, _ = oracle.avgpool2d_grad(gy, 3, 3, 3, 3, 2, 2, 1, 1, div_valid=True, scale=1.0)
+    q = np.array([[1, 11, 10], [101, 1111, 1010], [100, 1100, 1000]], np.float64) / 4.0
+    assert np.array_equal(gx[0, 0], q)
+    gx, _ = oracle.avgpool2d_grad(gy, 3, 3, 3, 3, 2, 2, 1, 1, div_valid=False, scale=1.0)
+    assert np.array_equal(gx[0, 0], q * 4.0)
+    # a stride above the window: cells between the windows get nothing
+    gx, _ = oracle.avgpool2d_grad(np.array([[[[2, 3]]]], np.float32), 1, 5, 1, 2, 1, 3)
+    assert gx[0, 0].tolist() == [[2, 2, 0, 3, 3]]
+
+
+@pytest.mark.parametrize("geom", [(3, 3, 1, 1, 1, 1), (3, 3, 2, 2, 1, 1), (2, 2, 2, 2, 0, 0), (4, 2, 3, 1, 2, 0), (1, 5, 1, 2, 0, 4),
+                                  (5, 5, 3, 2, 2, 1), (2, 3, 4, 5, 1, 2)])
+@pytest.mark.parametrize("div_valid", [False, True])
+def test_avgpool2d_grad_is_the_adjoint_of_the_pinned_forward_pooling(geom, div_valid):
+    """<pool2d_ex(x), gy> = <x, avgpool2d_grad(gy)> exactly on small integers with a power-of-two scale (the
+    divide-by-real-cells factors are rationals, so that case is held to 1e-12); at stride 1 without the
+    real-cell divisor the adjoint is itself a sliding add of gy over a plane padded by k - 1 - p; and the
+    gradient every window hands out adds up to gy times its number of real cells times f."""
+    kh, kw, sh, sw, ph, pw = geom
+    r = _rng(240 + kh * 11 + kw + sh)
+    x = r.integers(-4, 5, (2, 3, 11, 13)).astype(np.float32)
+    y, _ = oracle.pool2d_ex(oracle.OP_ADD, x, kh, kw, sh, sw, (ph, pw, ph, pw), div_valid, 0.5)
+    gy = r.integers(-3, 4, y.shape).astype(np.float32)
+    gx, mag = oracle.avgpool2d_grad(gy, 11, 13, kh, kw, sh, sw, ph, pw, div_valid, 0.5)
+    lhs, rhs = float((y * gy).sum()), float((gx * x).sum())
+    assert lhs == rhs if not div_valid else abs(lhs - rhs) <= 1e-12 * max(1.0, abs(lhs))
+    assert (mag >= np.abs(gx) - 1e-15).all()
+    if not div_valid:
+        ones, _ = oracle.pool2d_ex(oracle.OP_ADD, np.ones_like(x), kh, kw, sh, sw, (ph, pw, ph, pw), False, 1.0)   # real cells per window
+        assert gx.sum() == float((gy.astype(np.float64) * ones * 0.5).sum())
+    else:
+        assert abs(gx.sum() - 0.5 * float(gy.astype(np.float64).sum())) <= 1e-12 * np.abs(gy).sum()
+    if sh == 1 and sw == 1 and not div_valid:
+        slid, _ = oracle.pool2d_ex(oracle.OP_ADD, gy, kh, kw, 1, 1, (kh - 1 - ph, kw - 1 - pw, kh - 1 - ph, kw - 1 - pw), False, 0.5)
+        assert np.array_equal(slid, gx)
