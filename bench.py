@@ -327,6 +327,10 @@ def sweeps_table(torch, B, workloads, iters=20):
         ms = time_launches(torch, lambda: B.sws_maxpool2d_grad(x3, gy3, 3, 3, st, st, 1, 1, gx=gx3), iters)
         out["adjoints"]["cfg3_maxpool3x3_s%d_grad" % st] = {"us": round(ms * 1e3, 2), "GBps": round(nb / ms / 1e6, 1),
                                                            "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+        nb = 4 * 2048 * (112 * 112 + ho * ho)
+        ms = time_launches(torch, lambda: B.sws_avgpool2d_grad(gy3, 112, 112, 3, 3, st, st, 1, 1, 0, 1 / 9, gx=gx3), iters)
+        out["adjoints"]["cfg3_avgpool3x3_s%d_grad" % st] = {"us": round(ms * 1e3, 2), "GBps": round(nb / ms / 1e6, 1),
+                                                           "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
         del gy3
     del x3, gx3
     torch.cuda.empty_cache()

@@ -136,8 +136,6 @@ sws_status sws_pool2d(sws_op op, const float *x, float *y, int64_t N, int64_t C,
  *   x, gx : device, N*C*H*W floats     gy : device, N*C*Ho*Wo floats
  * gx is overwritten (cells no window chose get 0).  Deterministic: a cell adds the gradients of
  * the windows that chose it in a fixed order, without atomic operations.
- * Average pooling needs no entry point of its own: its adjoint is a sliding add of gy
- * (sws_slide1d_padded / sws_pool2d_ex with identity padding k - 1 - pad).
  * Errors: as sws_pool2d. */
 sws_status sws_maxpool2d_grad(const float *x, const float *gy, float *gx, int64_t N, int64_t C,
                               int64_t H, int64_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
@@ -175,6 +173,20 @@ sws_status sws_pool2d_ex(sws_op op, const float *x, float *y, int64_t N, int64_t
                          int64_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
                          int32_t pad_top, int32_t pad_left, int32_t pad_bottom, int32_t pad_right,
                          sws_divisor divisor, float scale, void *stream);
+
+/* The adjoint of average pooling (Section 2.3's pooling with the + operator, training side): of
+ * sws_pool2d_ex with SWS_OP_ADD, padding ph on top and bottom and pw left and right, and the same
+ * divisor and scale.  With loss = sum(gy * y),
+ *   gx[n,c,h,w] = sum over the windows (ho, wo) that hold (h, w) of f(ho, wo) * gy[n,c,ho,wo],
+ * f = scale, or scale / n(ho, wo) with n the number of cells of that window inside the plane
+ * (SWS_DIV_REAL_CELLS).  At stride 1 with SWS_DIV_SCALE this is itself a sliding add of gy over a
+ * plane padded by k - 1 - pad; at larger strides cells between windows receive 0.
+ *   gy : device, N*C*Ho*Wo floats     gx : device, N*C*H*W floats, overwritten
+ * Deterministic: a cell adds its windows in a fixed order, without atomic operations.
+ * Errors: as sws_pool2d; INVALID_ARG for an unknown divisor. */
+sws_status sws_avgpool2d_grad(const float *gy, float *gx, int64_t N, int64_t C, int64_t H, int64_t W,
+                              int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
+                              sws_divisor divisor, float scale, void *stream);
 
 /* 1-D convolution as a sliding dot product (Section 2.5; Eq. 4 per output), in the DNN
  * sense: cross-correlation, taps not flipped, zero padding, no bias.

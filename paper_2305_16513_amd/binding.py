@@ -19,7 +19,7 @@ _lib = None
 
 _i64, _i32, _f32, _vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
 
-EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_maxpool2d_grad", "sws_pool2d_16", "sws_pool2d_ex", "sws_conv1d", "sws_conv1d_grad_input", "sws_conv1d_grad_weight", "sws_conv2d", "sws_conv2d_grad_input", "sws_conv2d_grad_weight", "sws_copy", "sws_out_len",
+EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_maxpool2d_grad", "sws_avgpool2d_grad", "sws_pool2d_16", "sws_pool2d_ex", "sws_conv1d", "sws_conv1d_grad_input", "sws_conv1d_grad_weight", "sws_conv2d", "sws_conv2d_grad_input", "sws_conv2d_grad_weight", "sws_copy", "sws_out_len",
            "sws_status_string", "sws_set_option", "sws_version")
 
 
@@ -48,6 +48,9 @@ def lib():
         L.sws_pool2d.restype = ctypes.c_int
         L.sws_pool2d.argtypes = [ctypes.c_int, _vp, _vp, _i64, _i64, _i64, _i64,
                                  _i32, _i32, _i32, _i32, _i32, _i32, _f32, _vp]
+        L.sws_avgpool2d_grad.restype = ctypes.c_int
+        L.sws_avgpool2d_grad.argtypes = [_vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _i32, ctypes.c_int,
+                                         ctypes.c_float, _vp]
         L.sws_maxpool2d_grad.restype = ctypes.c_int
         L.sws_maxpool2d_grad.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _i32, _vp]
         L.sws_pool2d_16.restype = ctypes.c_int
@@ -224,6 +227,19 @@ def sws_maxpool2d_grad(x, gy, kh, kw, sh=1, sw=1, ph=0, pw=0, gx=None, stream=No
     gx = _out(gx, (n, c, h, wd), x, "gx")
     _check(lib().sws_maxpool2d_grad(x.data_ptr(), gy.data_ptr(), gx.data_ptr(), n, c, h, wd, kh, kw, sh, sw, ph, pw,
                                     _stream(stream)), "sws_maxpool2d_grad")
+    return gx
+
+
+def sws_avgpool2d_grad(gy, h, wd, kh, kw, sh=1, sw=1, ph=0, pw=0, divisor=0, scale=1.0, gx=None, stream=None):
+    """gy [N, C, Ho, Wo], (h, wd) = the pooled plane -> gx [N, C, H, W]: the adjoint of average pooling
+    (sws_pool2d_ex with SWS_OP_ADD, pads (ph, pw, ph, pw), the same divisor (0 = SWS_DIV_SCALE) and scale)."""
+    _dev(gy, "gy")
+    n, c, ho, wo = gy.shape
+    if (ho, wo) != (sws_out_len(h, kh, sh, ph), sws_out_len(wd, kw, sw, pw)):
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_avgpool2d_grad")
+    gx = _out(gx, (n, c, h, wd), gy, "gx")
+    _check(lib().sws_avgpool2d_grad(gy.data_ptr(), gx.data_ptr(), n, c, h, wd, kh, kw, sh, sw, ph, pw, int(divisor),
+                                    float(scale), _stream(stream)), "sws_avgpool2d_grad")
     return gx
 
 

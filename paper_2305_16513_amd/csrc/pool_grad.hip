@@ -297,6 +297,121 @@ __global__ __launch_bounds__(kThreads) void maxpool2d_grad_naive_kernel(const fl
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The adjoint of average pooling: gx[h, c] = sum over the windows that hold (h, c) of f * gy, with
+// f = scale, or scale / (cells of that window inside the plane).  The same band scheme without the
+// maxima: a workgroup stages the rows of f * gy its band's cells can ask for (zero where there is
+// no window) and every cell adds a fixed CA x CB rectangle of them, oldest window first.  Only the
+// rectangle's first row and first column can hold windows that end before the cell (when the
+// stride does not divide the window); they are masked.
+// ---------------------------------------------------------------------------------------------
+template <int KH, int KW, int SH, int SW>
+__global__ __launch_bounds__(kThreads) void avgpool2d_grad_kernel(const float *__restrict__ gy, float *__restrict__ gx, PgGeom g,
+                                                                  int64_t n_units, float scale, int div_real)
+{
+    const int kh = KH > 0 ? KH : g.kh, kw = KH > 0 ? KW : g.kw, sh = KH > 0 ? SH : g.sh, sw = KH > 0 ? SW : g.sw;
+    const int CA = KH > 0 ? (KH + SH - 1) / (SH > 0 ? SH : 1) : g.CA, CB = KH > 0 ? (KW + SW - 1) / (SW > 0 ? SW : 1) : g.CB;
+    extern __shared__ __attribute__((aligned(16))) float G[];     // [w_rows][PO]
+    const int64_t unit = blockIdx.x;
+    if (unit >= n_units) return;
+    const int64_t plane = unit / g.bands;
+    const int band = (int)(unit - plane * g.bands);
+    const int h0 = band * g.TH, h1 = h0 + g.TH < g.H ? h0 + g.TH : g.H;
+    const int wr0 = (h0 + g.ph) / sh - (CA - 1);     // the rows the band's first row reads start here
+    const int nrw = (h1 - 1 + g.ph) / sh - wr0 + 1;  // and those of its last row end here
+    const float *gp = gy + plane * (int64_t)g.Ho * g.Wo;
+    float *op = gx + plane * (int64_t)g.H * g.W;
+    const float inv_po = 1.0f / (float)g.PO, inv_w = 1.0f / (float)g.W;
+    {
+        constexpr int U = 4;
+        for (int j0 = threadIdx.x; j0 < nrw * g.PO; j0 += kThreads * U) {
+            float v[U];
+            bool ok[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int j = j0 + u * kThreads;
+                const int r = (int)(((float)j + 0.5f) * inv_po), wo = j - r * g.PO - g.colpad;
+                const int ho = wr0 + r;
+                ok[u] = j < nrw * g.PO && (unsigned)ho < (unsigned)g.Ho && (unsigned)wo < (unsigned)g.Wo;
+                v[u] = gp[ok[u] ? ho * g.Wo + wo : 0];
+                if (div_real) {                      // cells of window (ho, wo) inside the plane
+                    const int r0 = ho * sh - g.ph, c0 = wo * sw - g.pw;
+                    const int nr = (r0 + kh < g.H ? r0 + kh : g.H) - (r0 > 0 ? r0 : 0);
+                    const int nc = (c0 + kw < g.W ? c0 + kw : g.W) - (c0 > 0 ? c0 : 0);
+                    v[u] = ok[u] ? v[u] * (scale / (float)(nr * nc)) : 0.0f;
+                } else {
+                    v[u] = ok[u] ? v[u] * scale : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int j = j0 + u * kThreads;
+                if (j < nrw * g.PO) G[j] = v[u];
+            }
+        }
+    }
+    __syncthreads();
+    const int nrows = h1 - h0;
+    for (int i = threadIdx.x; i < nrows * g.W; i += kThreads) {
+        const int r = (int)(((float)i + 0.5f) * inv_w), c = i - r * g.W;
+        const int h = h0 + r;
+        const int a_hi = (h + g.ph) / sh, b_hi = (c + g.pw) / sw;
+        const int top = (a_hi - wr0 - CA + 1) * g.PO + b_hi;               // column + colpad - (CB - 1)
+        // the oldest candidate row / column ends before the cell unless the cell's offset in it is below kh / kw
+        const bool row0 = (h + g.ph) - (a_hi - CA + 1) * sh < kh, col0 = (c + g.pw) - (b_hi - CB + 1) * sw < kw;
+        float acc = 0.0f;
+        if (KH > 0) {
+            constexpr int NA = KH > 0 ? (KH + SH - 1) / SH : 1, NB = KH > 0 ? (KW + SW - 1) / SW : 1;
+            float gv[NA * NB];
+#pragma unroll
+            for (int da = 0; da < NA; ++da)
+#pragma unroll
+                for (int db = 0; db < NB; ++db) gv[da * NB + db] = G[top + da * g.PO + db];
+#pragma unroll
+            for (int da = 0; da < NA; ++da)
+#pragma unroll
+                for (int db = 0; db < NB; ++db) acc += ((da > 0 || row0) && (db > 0 || col0)) ? gv[da * NB + db] : 0.0f;
+        } else {
+            for (int da = 0; da < CA; ++da)
+                for (int db = 0; db < CB; ++db) acc += ((da > 0 || row0) && (db > 0 || col0)) ? G[top + da * g.PO + db] : 0.0f;
+        }
+        __builtin_nontemporal_store(acc, op + (int64_t)h * g.W + c);
+    }
+}
+
+// Direct evaluation for planes whose window rows do not fit LDS.
+__global__ __launch_bounds__(kThreads) void avgpool2d_grad_naive_kernel(const float *__restrict__ gy, float *__restrict__ gx,
+                                                                        int64_t planes, int H, int W, int Ho, int Wo, int kh,
+                                                                        int kw, int sh, int sw, int ph, int pw, float scale,
+                                                                        int div_real)
+{
+    const int64_t total = planes * (int64_t)H * W;
+    for (int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x; o < total; o += (int64_t)gridDim.x * kThreads) {
+        const int c = (int)(o % W);
+        const int h = (int)((o / W) % H);
+        const int64_t p = o / ((int64_t)W * H);
+        int a_lo = ceil_div(h + ph - kh + 1, sh), a_hi = floor_div(h + ph, sh);
+        int b_lo = ceil_div(c + pw - kw + 1, sw), b_hi = floor_div(c + pw, sw);
+        if (a_lo < 0) a_lo = 0;
+        if (b_lo < 0) b_lo = 0;
+        if (a_hi > Ho - 1) a_hi = Ho - 1;
+        if (b_hi > Wo - 1) b_hi = Wo - 1;
+        float acc = 0.0f;
+        for (int ho = a_lo; ho <= a_hi; ++ho)
+            for (int wo = b_lo; wo <= b_hi; ++wo) {
+                float f = scale;
+                if (div_real) {
+                    const int r0 = ho * sh - ph, c0 = wo * sw - pw;
+                    const int nr = (r0 + kh < H ? r0 + kh : H) - (r0 > 0 ? r0 : 0);
+                    const int nc = (c0 + kw < W ? c0 + kw : W) - (c0 > 0 ? c0 : 0);
+                    f = scale / (float)(nr * nc);
+                }
+                acc += gy[(p * Ho + ho) * (int64_t)Wo + wo] * f;
+            }
+        gx[o] = acc;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_maxpool2d_grad(const float *x, const float *gy, float *gx, int64_t planes, int64_t H, int64_t W,
@@ -362,6 +477,56 @@ hipError_t launch_maxpool2d_grad(const float *x, const float *gy, float *gx, int
     if (grid > 1048576) grid = 1048576;
     hipLaunchKernelGGL(maxpool2d_grad_naive_kernel, dim3((unsigned)grid), dim3(kThreads), 0, s, x, gy, gx, planes, (int)H,
                        (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw);
+    return hipGetLastError();
+}
+
+hipError_t launch_avgpool2d_grad(const float *gy, float *gx, int64_t planes, int64_t H, int64_t W, int64_t Ho, int64_t Wo,
+                                 int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw, int div_real,
+                                 float scale, hipStream_t s)
+{
+    PgGeom g;
+    g.H = (int)H; g.W = (int)W; g.Ho = (int)Ho; g.Wo = (int)Wo; g.kh = kh; g.kw = kw; g.sh = sh; g.sw = sw; g.ph = ph; g.pw = pw;
+    g.pwl = pw; g.PX = 0; g.x_rows = 0; g.cwx = g.kmx = g.cwg = g.kmg = 0;
+    g.CA = (kh + sh - 1) / sh;
+    g.CB = (kw + sw - 1) / sw;
+    g.colpad = g.CB - 1;
+    const int last_col = (int)((W - 1 + pw) / sw);   // the last window column a cell can ask for
+    g.PO = g.colpad + (last_col + 1 > (int)Wo ? last_col + 1 : (int)Wo);
+    // rows per band: a band of th rows asks for at most ceil((th - 1) / sh) + CA window rows; 16 KB
+    // of LDS per workgroup keeps several workgroups on a compute unit
+    constexpr int kLds = 16 * 1024;
+    auto plan = [&](int th) {
+        g.w_rows = (th - 1 + sh - 1) / sh + g.CA;
+        g.slice = g.w_rows * g.PO;
+        return (size_t)g.slice * 4 <= (size_t)kLds;
+    };
+    int TH = H < 64 ? (int)H : 64;
+    while (TH >= 1 && !plan(TH)) --TH;
+    if (TH >= 1) {                                   // bands of equal height
+        const int nb = (int)((H + TH - 1) / TH);
+        TH = (int)((H + nb - 1) / nb);
+        plan(TH);
+    }
+    if (TH >= 1 && g_opt.pool2d_variant != 1 && H * W < (1 << 20) && Ho * Wo < (1 << 20)) {
+        g.TH = TH;
+        g.bands = (int)((H + TH - 1) / TH);
+        const int64_t n_units = planes * g.bands;
+        if (n_units <= 2147483647LL) {
+#define SWS_AG(KH, KW, SH, SW)                                                                                   \
+    hipLaunchKernelGGL((avgpool2d_grad_kernel<KH, KW, SH, SW>), dim3((unsigned)n_units), dim3(kThreads),             \
+                       (size_t)g.slice * 4, s, gy, gx, g, n_units, scale, div_real)
+            if (kh == 3 && kw == 3 && sh == 1 && sw == 1) SWS_AG(3, 3, 1, 1);
+            else if (kh == 3 && kw == 3 && sh == 2 && sw == 2) SWS_AG(3, 3, 2, 2);
+            else if (kh == 2 && kw == 2 && sh == 2 && sw == 2) SWS_AG(2, 2, 2, 2);
+            else SWS_AG(0, 0, 1, 1);
+#undef SWS_AG
+            return hipGetLastError();
+        }
+    }
+    int64_t grid = (planes * H * W + kThreads - 1) / kThreads;
+    if (grid > 1048576) grid = 1048576;
+    hipLaunchKernelGGL(avgpool2d_grad_naive_kernel, dim3((unsigned)grid), dim3(kThreads), 0, s, gy, gx, planes, (int)H, (int)W,
+                       (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw, scale, div_real);
     return hipGetLastError();
 }
 

@@ -148,6 +148,27 @@ sws_status sws_pool2d(sws_op op, const float *x, float *y, int64_t N, int64_t C,
                                        (hipStream_t)stream));
 }
 
+sws_status sws_avgpool2d_grad(const float *gy, float *gx, int64_t N, int64_t C, int64_t H, int64_t W, int32_t kh,
+                              int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw, sws_divisor divisor, float scale,
+                              void *stream)
+{
+    if (N < 0 || C < 0 || H < 0 || W < 0) return SWS_ERR_INVALID_ARG;
+    if (kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0) return SWS_ERR_INVALID_ARG;
+    if (ph >= kh || pw >= kw) return SWS_ERR_INVALID_ARG;
+    if (divisor != SWS_DIV_SCALE && divisor != SWS_DIV_REAL_CELLS) return SWS_ERR_INVALID_ARG;
+    if (H > kMaxDim || W > kMaxDim) return SWS_ERR_INVALID_ARG;
+    const int64_t Ho = sws_out_len(H, kh, sh, ph, 1), Wo = sws_out_len(W, kw, sw, pw, 1);
+    if (Ho < 1 || Wo < 1) return SWS_ERR_INVALID_ARG;
+    int64_t planes, n_in, n_out;
+    if (!mul3(N, C, 1, &planes) || !mul3(planes, H, W, &n_in) || !mul3(planes, Ho, Wo, &n_out))
+        return SWS_ERR_INVALID_ARG;
+    if (H * W > kMaxDim) return SWS_ERR_UNSUPPORTED;
+    if (planes == 0) return SWS_OK;
+    if (!gy || !gx) return SWS_ERR_INVALID_ARG;
+    return from_hip(sws::launch_avgpool2d_grad(gy, gx, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw,
+                                               divisor == SWS_DIV_REAL_CELLS ? 1 : 0, scale, (hipStream_t)stream));
+}
+
 sws_status sws_maxpool2d_grad(const float *x, const float *gy, float *gx, int64_t N, int64_t C, int64_t H, int64_t W,
                               int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw, void *stream)
 {

@@ -189,6 +189,11 @@ def test_new_entry_points_argument_checks(L):
         ("x", "gy", "gx", "N", "C", "H", "W", "kh", "kw", "sh", "sw", "ph", "pw", "s"),
         (one, one, one, 1, 3, 8, 8, 3, 3, 1, 1, 1, 1, nul))])
     assert mp(N=0) == 0 and mp(ph=3) == 1 and mp(kw=0) == 1 and mp(gx=nul) == 1 and mp(kh=12) == 1
+    L.sws_avgpool2d_grad.argtypes = [ctypes.c_void_p] * 2 + [i64] * 4 + [i32] * 6 + [ctypes.c_int, f32, ctypes.c_void_p]
+    ap = lambda **kw: L.sws_avgpool2d_grad(*[kw.get(n, v) for n, v in zip(
+        ("gy", "gx", "N", "C", "H", "W", "kh", "kw", "sh", "sw", "ph", "pw", "div", "scale", "s"),
+        (one, one, 1, 3, 8, 8, 3, 3, 2, 2, 1, 1, 0, 1.0, nul))])
+    assert ap(N=0) == 0 and ap(ph=3) == 1 and ap(sh=0) == 1 and ap(gx=nul) == 1 and ap(kh=12) == 1 and ap(div=2) == 1
     L.sws_pool2d_16.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, i64, i64, i64, i64,
                                 i32, i32, i32, i32, i32, i32, f32, ctypes.c_void_p]
     assert L.sws_pool2d_16(0, 1, one, one, 0, 3, 8, 8, 3, 3, 1, 1, 1, 1, 1.0, nul) == 0

@@ -86,3 +86,70 @@ def test_argument_checks(B):
         B.sws_maxpool2d_grad(x, torch.zeros((1, 2, 7, 7), device="cuda"), 3, 3, 1, 1, 1, 1)
     assert B.lib().sws_maxpool2d_grad(x.data_ptr(), x.data_ptr(), None, 1, 2, 8, 8, 3, 3, 1, 1, 1, 1, None) == B.SWS_ERR_INVALID_ARG
     assert B.lib().sws_maxpool2d_grad(x.data_ptr(), x.data_ptr(), x.data_ptr(), 1, 2, 8, 8, 3, 3, 1, 1, 3, 1, None) == B.SWS_ERR_INVALID_ARG
+
+
+# ------------------------------------------------------------------ the adjoint of average pooling
+def _check_avg(B, gy, h, wd, geom, div, scale, what):
+    gx = to_host(B.sws_avgpool2d_grad(to_gpu(gy), h, wd, *geom, divisor=div, scale=scale))
+    ref, mag = oracle.avgpool2d_grad(gy, h, wd, *geom, div_valid=bool(div), scale=scale)
+    assert_within_tol(gx, ref, mag, what)
+    return gx, ref
+
+
+@pytest.mark.parametrize("div", [0, 1])
+@pytest.mark.parametrize("geom", GEOMS)
+@pytest.mark.parametrize("shape", [(2, 3, 37, 53), (1, 2, 112, 112), (3, 1, 16, 200), (1, 2, 129, 19), (1, 1, 1, 1), (2, 2, 5, 4000)])
+def test_avgpool2d_grad_geometries(B, geom, shape, div):
+    kh, kw, sh, sw, ph, pw = geom
+    if kh > shape[2] + 2 * ph or kw > shape[3] + 2 * pw:
+        pytest.skip("window larger than plane")
+    r = np.random.Generator(np.random.PCG64(kh * 100 + kw * 10 + sh + shape[2] + shape[3] + div))
+    ho, wo = (shape[2] + 2 * ph - kh) // sh + 1, (shape[3] + 2 * pw - kw) // sw + 1
+    gy = r.standard_normal((shape[0], shape[1], ho, wo), dtype=np.float32)
+    _check_avg(B, gy, shape[2], shape[3], geom, div, 1.0 if div else 1.0 / (kh * kw), "avg %s %s div %d" % (geom, shape, div))
+
+
+@pytest.mark.parametrize("geom", [(3, 3, 1, 1, 1, 1), (3, 3, 2, 2, 1, 1), (2, 2, 2, 2, 0, 0), (5, 3, 2, 1, 2, 1), (2, 3, 4, 5, 1, 2)])
+def test_avgpool2d_grad_is_exact_on_integer_gradients_and_agrees_with_direct_evaluation(B, geom):
+    kh, kw, sh, sw, ph, pw = geom
+    ho, wo = (40 + 2 * ph - kh) // sh + 1, (45 + 2 * pw - kw) // sw + 1
+    gy = workloads.integer_valued((2, 3, ho, wo), -3, 3, 19)
+    gx, ref = _check_avg(B, gy, 40, 45, geom, 0, 0.25, "integers %s" % (geom,))
+    assert np.array_equal(gx.astype(np.float64), ref)
+    B.sws_set_option("pool2d_variant", 1)
+    try:
+        direct = to_host(B.sws_avgpool2d_grad(to_gpu(gy), 40, 45, *geom, divisor=0, scale=0.25))
+    finally:
+        B.sws_set_option("pool2d_variant", 0)
+    assert np.array_equal(gx, direct)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_avgpool2d_grad_random(B, seed):
+    r = np.random.Generator(np.random.PCG64(9100 + seed))
+    kh, kw = int(r.integers(1, 8)), int(r.integers(1, 8))
+    sh, sw = int(r.integers(1, 6)), int(r.integers(1, 6))
+    ph, pw = int(r.integers(0, kh)), int(r.integers(0, kw))
+    h = max(1, kh - 2 * ph) + int(r.integers(0, 130))
+    wd = max(1, kw - 2 * pw) + int(r.integers(0, 300 if seed % 4 else 6000))
+    n, c = int(r.integers(1, 3)), int(r.integers(1, 4))
+    ho, wo = (h + 2 * ph - kh) // sh + 1, (wd + 2 * pw - kw) // sw + 1
+    gy = r.standard_normal((n, c, ho, wo), dtype=np.float32)
+    div = seed % 2
+    _check_avg(B, gy, h, wd, (kh, kw, sh, sw, ph, pw), div, 0.37, "seed %d: %dx%d s%dx%d p%dx%d plane %dx%d div %d" % (seed, kh, kw, sh, sw, ph, pw, h, wd, div))
+
+
+@pytest.mark.parametrize("stride", [1, 2])
+def test_avgpool2d_grad_cfg3_shaped_planes(B, stride):
+    ho = (112 + 2 - 3) // stride + 1
+    gy = np.random.Generator(np.random.PCG64(5 + stride)).standard_normal((2, 8, ho, ho), dtype=np.float32)
+    _check_avg(B, gy, 112, 112, (3, 3, stride, stride, 1, 1), 1, 1.0, "cfg3 planes, stride %d" % stride)
+
+
+def test_avgpool2d_grad_argument_checks(B):
+    gy = to_gpu(np.zeros((1, 1, 4, 4), np.float32))
+    with pytest.raises(B.SwsError):
+        B.sws_avgpool2d_grad(gy, 9, 9, 3, 3, 2, 2, 1, 1)                 # gy is not the pooled shape (5 x 5)
+    with pytest.raises(B.SwsError):
+        B.sws_avgpool2d_grad(gy, 4, 4, 3, 3, 1, 1, 1, 1, divisor=7)
+    assert B.sws_avgpool2d_grad(to_gpu(np.zeros((0, 3, 4, 4), np.float32)), 4, 4, 3, 3, 1, 1, 1, 1).shape == (0, 3, 4, 4)
