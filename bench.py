@@ -460,6 +460,12 @@ def run_only(torch, B, workloads, name, steps):
         fn = {"forward": lambda: B.sws_conv2d(xs, ws, st, st, 1, 1, y=ys),
               "grad_input": lambda: B.sws_conv2d_grad_input(gs, ws, hh, hh, st, st, 1, 1, gx=gxs),
               "grad_weight": lambda: B.sws_conv2d_grad_weight(xs, gs, 3, 3, st, st, 1, 1, gw=gws)}[what]
+    elif name in ("grad_cfg3_avgpool_s1", "grad_cfg3_avgpool_s2"):
+        s = int(name[-1])
+        ho = 112 if s == 1 else 56
+        gy = torch.empty(32, 64, ho, ho, device="cuda").normal_()
+        gx = torch.empty(32, 64, 112, 112, device="cuda")
+        fn = lambda: B.sws_avgpool2d_grad(gy, 112, 112, 3, 3, s, s, 1, 1, 0, 1 / 9, gx=gx)
     elif name in ("grad_cfg3_maxpool_s1", "grad_cfg3_maxpool_s2"):
         x3 = g(workloads.make(3)[0])
         s = int(name[-1])

@@ -188,10 +188,10 @@ __global__ __launch_bounds__(kThreads) void maxpool2d_grad_kernel(const float *_
         }
         // ---- 1. the position of every window's maximum (0xFFFF in the border)
         for (int i = lane; i < b.nrw * g.PO; i += kThreads) {
-            const int r = (int)(((float)i + 0.5f) * inv_po), wo = i - r * g.PO - g.colpad;
+            const int r = (int)(((float)i + 0.5f) * inv_po), wo = i - __mul24(r, g.PO) - g.colpad;
             const int ho = b.wr0 + r;
             const bool valid = ho >= 0 && ho < g.Ho && wo >= 0 && wo < g.Wo;
-            const int base = valid ? (ho - b.ho_lo) * sh * g.PX + g.pwl - g.pw + wo * sw : 0;   // the window's first cell
+            const int base = valid ? __mul24((ho - b.ho_lo) * sh, g.PX) + g.pwl - g.pw + wo * sw : 0;   // the window's first cell
             float best = ninf;
             int at = base;
             if (KH > 0) {
@@ -226,10 +226,10 @@ __global__ __launch_bounds__(kThreads) void maxpool2d_grad_kernel(const float *_
         //      CA x CB rectangle of windows ending at row (h + ph) / sh, column (c + pw) / sw
         const int nrows = b.h1 - b.h0;
         for (int i = lane; i < nrows * g.W; i += kThreads) {
-            const int r = (int)(((float)i + 0.5f) * inv_w), c = i - r * g.W;
+            const int r = (int)(((float)i + 0.5f) * inv_w), c = i - __mul24(r, g.W);
             const int h = b.h0 + r;
-            const int me = (h - b.xr_lo) * g.PX + g.pwl + c;
-            const int top = ((h + g.ph) / sh - b.wr0 - CA + 1) * g.PO + (c + g.pw) / sw;   // column + colpad - (CB - 1)
+            const int me = __mul24(h - b.xr_lo, g.PX) + g.pwl + c;
+            const int top = __mul24((h + g.ph) / sh - b.wr0 - CA + 1, g.PO) + (c + g.pw) / sw;   // column + colpad - (CB - 1)
             float acc = 0.0f;
             if (KH > 0) {
                 constexpr int NA = KH > 0 ? (KH + SH - 1) / SH : 1, NB = KH > 0 ? (KW + SW - 1) / SW : 1;
@@ -251,7 +251,7 @@ __global__ __launch_bounds__(kThreads) void maxpool2d_grad_kernel(const float *_
                         acc += (int)IDX[t] == me ? G[t] : 0.0f;
                     }
             }
-            __builtin_nontemporal_store(acc, op + (int64_t)h * g.W + c);
+            __builtin_nontemporal_store(acc, op + (__mul24(h, g.W) + c));   // a plane has < 2^20 cells
         }
     }
 }
@@ -330,10 +330,10 @@ __global__ __launch_bounds__(kThreads) void avgpool2d_grad_kernel(const float *_
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int j = j0 + u * kThreads;
-                const int r = (int)(((float)j + 0.5f) * inv_po), wo = j - r * g.PO - g.colpad;
+                const int r = (int)(((float)j + 0.5f) * inv_po), wo = j - __mul24(r, g.PO) - g.colpad;
                 const int ho = wr0 + r;
                 ok[u] = j < nrw * g.PO && (unsigned)ho < (unsigned)g.Ho && (unsigned)wo < (unsigned)g.Wo;
-                v[u] = gp[ok[u] ? ho * g.Wo + wo : 0];
+                v[u] = gp[ok[u] ? __mul24(ho, g.Wo) + wo : 0];
                 if (div_real) {                      // cells of window (ho, wo) inside the plane
                     const int r0 = ho * sh - g.ph, c0 = wo * sw - g.pw;
                     const int nr = (r0 + kh < g.H ? r0 + kh : g.H) - (r0 > 0 ? r0 : 0);
@@ -353,12 +353,13 @@ __global__ __launch_bounds__(kThreads) void avgpool2d_grad_kernel(const float *_
     __syncthreads();
     const int nrows = h1 - h0;
     for (int i = threadIdx.x; i < nrows * g.W; i += kThreads) {
-        const int r = (int)(((float)i + 0.5f) * inv_w), c = i - r * g.W;
+        const int r = (int)(((float)i + 0.5f) * inv_w), c = i - __mul24(r, g.W);
         const int h = h0 + r;
         const int a_hi = (h + g.ph) / sh, b_hi = (c + g.pw) / sw;
-        const int top = (a_hi - wr0 - CA + 1) * g.PO + b_hi;               // column + colpad - (CB - 1)
+        const int top = __mul24(a_hi - wr0 - CA + 1, g.PO) + b_hi;        // column + colpad - (CB - 1)
         // the oldest candidate row / column ends before the cell unless the cell's offset in it is below kh / kw
-        const bool row0 = (h + g.ph) - (a_hi - CA + 1) * sh < kh, col0 = (c + g.pw) - (b_hi - CB + 1) * sw < kw;
+        constexpr bool kExact = KH > 0 && KH % (SH > 0 ? SH : 1) == 0 && KW % (SW > 0 ? SW : 1) == 0;   // every candidate covers the cell
+        const bool row0 = kExact || (h + g.ph) - (a_hi - CA + 1) * sh < kh, col0 = kExact || (c + g.pw) - (b_hi - CB + 1) * sw < kw;
         float acc = 0.0f;
         if (KH > 0) {
             constexpr int NA = KH > 0 ? (KH + SH - 1) / SH : 1, NB = KH > 0 ? (KW + SW - 1) / SW : 1;
@@ -375,7 +376,7 @@ __global__ __launch_bounds__(kThreads) void avgpool2d_grad_kernel(const float *_
             for (int da = 0; da < CA; ++da)
                 for (int db = 0; db < CB; ++db) acc += ((da > 0 || row0) && (db > 0 || col0)) ? G[top + da * g.PO + db] : 0.0f;
         }
-        __builtin_nontemporal_store(acc, op + (int64_t)h * g.W + c);
+        __builtin_nontemporal_store(acc, op + (__mul24(h, g.W) + c));      // a plane has < 2^20 cells
     }
 }
 
