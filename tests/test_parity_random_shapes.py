@@ -303,3 +303,26 @@ def test_conv2d_grad_input_strided_random(B, seed):
     gx = to_host(B.sws_conv2d_grad_input(to_gpu(g), to_gpu(w), h, wd, sh, sw, ph, pw))
     rx, mx = oracle.conv2d_grad_input(g, w, h, wd, sh, sw, ph, pw)
     assert_within_tol(gx, rx, mx, "seed %d: N %d Cin %d H %d W %d Cout %d k %dx%d s %dx%d p %dx%d" % (seed, n, cin, h, wd, cout, kh, kw, sh, sw, ph, pw))
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_conv2d_1x1_random(B, seed):
+    """1 x 1 kernels (planes taken as one long row, four channel blocks per barrier pair where the
+    channel count allows), forward and both adjoints, strides 1 and 2."""
+    r = _rng(8200 + seed)
+    cin = int(r.choice([32, 64, 96, 128, 8, 24, 40, 33]))
+    cout = int(r.integers(1, 130))
+    h, wd = int(r.integers(1, 40)), int(r.integers(1, 70))
+    n = int(r.integers(1, 4))
+    s = 1 if seed % 3 else 2
+    ho, wo = (h - 1) // s + 1, (wd - 1) // s + 1
+    x = r.standard_normal((n, cin, h, wd), dtype=np.float32)
+    w = (r.standard_normal((cout, cin, 1, 1), dtype=np.float32) * np.float32(0.2)).astype(np.float32)
+    g = r.standard_normal((n, cout, ho, wo), dtype=np.float32)
+    what = "seed %d: N %d Cin %d Cout %d plane %dx%d stride %d" % (seed, n, cin, cout, h, wd, s)
+    ry, my = oracle.conv2d(x, w, s, s, 0, 0)
+    assert_within_tol(to_host(B.sws_conv2d(to_gpu(x), to_gpu(w), s, s, 0, 0)), ry, my, "forward " + what)
+    rx, mx = oracle.conv2d_grad_input(g, w, h, wd, s, s, 0, 0)
+    assert_within_tol(to_host(B.sws_conv2d_grad_input(to_gpu(g), to_gpu(w), h, wd, s, s, 0, 0)), rx, mx, "grad_input " + what)
+    rw, mw = oracle.conv2d_grad_weight(x, g, 1, 1, s, s, 0, 0)
+    assert_within_tol(to_host(B.sws_conv2d_grad_weight(to_gpu(x), to_gpu(g), 1, 1, s, s, 0, 0)), rw, mw, "grad_weight " + what)
