@@ -52,6 +52,10 @@ struct ConvGeom {
                                                       //   stored kernel) from one row / one tap of this launch's kernel to the next
     int yH, yW, ysh, ysw, yh0, yw0;                   // general instance: output (oh, ow) is stored at row yh0 + oh*ysh, column
                                                       //   yw0 + ow*ysw of planes of yH x yW (a phase of a strided adjoint)
+    int vw, xsh, xsw, xH, xW;                         // general instance, 1 x 1 kernels: the launch's plane is a row of cells
+                                                      //   numbered row-major over rows of vw cells; cell (r, c) of those rows is
+                                                      //   input element (r*xsh, c*xsw) of the stored xH x xW plane, and output
+                                                      //   row / column (r, c) before ysh / ysw apply.  vw = 2^30: no renumbering
 };
 
 // x / d for 0 <= x < 2^20 and 1 <= d < 2^12, exact, a handful of VALU ops instead of the
@@ -298,7 +302,7 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
     const int co0 = blockIdx.y * kCoTile;
     const int64_t n = blockIdx.z;
     const int KT = KTT > 0 ? KTT : g.kh * g.kw;
-    const int plane = g.H * g.W;
+    const int plane = GEN ? g.xH * g.xW : g.H * g.W;
     const float *xn = x + n * g.Cin * (int64_t)plane;
 
     int oh_first, ow_first, p_base = 0;
@@ -349,7 +353,12 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
         const int gh = row0 + rr, cc = ch * 64 + lane, gw = col0 + cc;
         const bool act = seg < nseg && cc < g.Wt;
         xl[s] = act ? (rr * g.Wt + cc) * XP + ci : -1;
-        xg[s] = (act && gh >= 0 && gh < g.H && gw >= 0 && gw < g.W) ? ci * plane + gh * g.W + gw : -1;
+        if constexpr (GEN) {
+            const int vr = gw >= 0 ? gw / g.vw : 0, vc = gw - vr * g.vw;     // (0, gw) unless the plane is renumbered
+            xg[s] = (act && gh >= 0 && gh < g.H && gw >= 0 && gw < g.W) ? ci * plane + (gh + vr) * g.xsh * g.xW + vc * g.xsw : -1;
+        } else {
+            xg[s] = (act && gh >= 0 && gh < g.H && gw >= 0 && gw < g.W) ? ci * plane + gh * g.W + gw : -1;
+        }
     }
     // ---- weight staging plan: thread (co = tid / 8, ci = tid % 8) moves the KT taps of one
     // (output channel, input channel) pair: KT contiguous floats in memory, and in LDS the
@@ -459,7 +468,8 @@ __global__ __launch_bounds__(WAVES * 64, (2 * WAVES + 3) / 4) void conv2d_mfma_c
     if (!pok) return;
     if constexpr (GEN) {
         float *yn = y + n * g.Cout * (int64_t)g.yH * g.yW;
-        const int64_t at = (int64_t)(g.yh0 + oh * g.ysh) * g.yW + g.yw0 + ow * g.ysw;
+        const int vr = ow / g.vw, vc = ow - vr * g.vw;
+        const int64_t at = (int64_t)(g.yh0 + (oh + vr) * g.ysh) * g.yW + g.yw0 + vc * g.ysw;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int co = co0 + wm * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
@@ -565,7 +575,7 @@ bool c8_prepare(C8Launch *L, int64_t N)
     const int xfloats = (g.NRows * g.Wt * 12 + 3) / 4 * 4;
     const size_t lds1 = 4 * ((size_t)xfloats + (size_t)KT * kCoTile * 12);
     // few taps: four channel blocks per barrier pair, if they fit
-    const bool general = g.Cin % 8 != 0 || g.wadj;    // the general instance stages one channel block per barrier pair
+    const bool general = g.Cin % 8 != 0 || g.wadj || g.vw != (1 << 30);    // the general instance stages one channel block per barrier pair
     // (the general instance has it for 1 x 1 kernels only: the adjoint of a 1 x 1 convolution)
     const bool nb4 = ((!general && KT == 3 && g.kw == 3) || KT == 1) && g.Cin % 32 == 0 && 8 * g.NRows * g.CH <= 32 &&
                      4 * lds1 <= 64 * 1024 && g_opt.conv2d_variant != 5;
@@ -668,6 +678,15 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
     g.wstride = KT; g.wofs = 0; g.accum = 0; g.wadj = wadj;
     g.wlast = KT - 1; g.wrs = kw; g.wcs = 1;
     g.yH = (int)Ho; g.yW = (int)Wo; g.ysh = 1; g.ysw = 1; g.yh0 = 0; g.yw0 = 0;
+    g.vw = 1 << 30; g.xsh = 1; g.xsw = 1; g.xH = (int)H; g.xW = (int)W;
+    // A strided 1 x 1 kernel without padding reads every sh-th row and sw-th column and nothing else:
+    // the cells it reads, numbered row-major, are one long row for a stride-1 launch of the general
+    // instance (which would otherwise stage the skipped cells too).
+    if (KT == 1 && (sh > 1 || sw > 1) && ph == 0 && pw == 0 && !wadj && Cin * H * W < 2147483647LL) {
+        g.vw = (int)Wo; g.xsh = sh; g.xsw = sw;
+        g.H = 1; g.W = (int)(Ho * Wo); g.Ho = 1; g.Wo = (int)(Ho * Wo);
+        g.sh = 1; g.sw = 1;
+    }
     // Up to 36 adjacent taps at stride 1 the scalar-read kernel does the whole kernel in one pass,
     // which beats a chain of five or more launches (5 x 5 on [32,64,56,56]: 0.27 ms against 0.41 ms).
     const bool one_pass = !wadj && plain && KT > 9 && KT <= 36 && Cin % 4 == 0 && g_opt.conv2d_variant != 6;
@@ -757,10 +776,16 @@ hipError_t launch_conv2d_grad_input_phases(const float *gy, const float *wgt, fl
             g.wstride = KTF; g.wofs = 0; g.wadj = 1;
             g.wrs = sh * kw; g.wcs = sw;
             g.yH = (int)H; g.yW = (int)W; g.ysh = sh; g.ysw = sw; g.yh0 = h0; g.yw0 = c0;
+            g.vw = 1 << 30; g.xsh = 1; g.xsw = 1; g.xH = (int)Ho; g.xW = (int)Wo;
             const int last = (rh + sh * (KA - 1)) * kw + rc + sw * (KB - 1);     // the sub-kernel's last tap, read first
             // out[i][j] = sum_{u,v} K[u][v] * gy[i + i0 - (KA-1) + u][j + j0 - (KB-1) + v]: padding KA-1-i0, KB-1-j0
             const int PA = KA - 1 - i0, PB = KB - 1 - j0;
             const int KT = KA * KB;
+            if (KT == 1 && PA == 0 && PB == 0 && nH == Ho && nW == Wo && Ho > 1) {
+                // a one-tap phase maps gy cell for cell onto its cells of gx: one long row (full tiles on narrow planes)
+                g.vw = (int)Wo;
+                g.H = 1; g.W = (int)(Ho * Wo); g.Ho = 1; g.Wo = (int)(Ho * Wo);
+            }
             const int rows_per = KT <= 9 ? KA : (KB <= 9 ? 9 / KB : 1);
             const int taps_per = KB <= 9 ? KB : 9;
             const int row_chunks = (KA + rows_per - 1) / rows_per, run_chunks = (KB + taps_per - 1) / taps_per;
