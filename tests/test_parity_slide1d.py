@@ -302,3 +302,18 @@ def test_more_than_2_to_the_32_elements(B):
     assert np.array_equal(y[sample].float().cpu().numpy().astype(np.float64), ref)
     del y, xb
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("variant", [0, 1, 3, 4])
+def test_copy_is_bit_exact_for_every_variant_and_ragged_sizes(B, variant):
+    """sws_copy (the calibration copy behind the bandwidth ceilings): whole tiles, a ragged tail, sizes below one tile."""
+    import torch
+    B.sws_set_option("copy_variant", variant)
+    try:
+        for n in (1, 255, 256, 257, 4095, 4096, 4097, 3 * 4096 + 1000, (1 << 20) + 3):
+            src = torch.arange(n, device="cuda", dtype=torch.float32) * 0.5 - 7.0
+            dst = torch.full((n + 8,), -1.0, device="cuda")
+            B.sws_copy(src, dst[:n])
+            assert torch.equal(dst[:n], src) and bool((dst[n:] == -1.0).all()), "variant %d n %d" % (variant, n)
+    finally:
+        B.sws_set_option("copy_variant", 0)
