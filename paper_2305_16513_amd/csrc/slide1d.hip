@@ -45,30 +45,34 @@ __device__ __forceinline__ void wave_lds_sync()
 // ------------------------------------------------------------------------------------------
 // Small windows: y[i] = x[i] (+) x[i+1] (+) ... (+) x[i+W-1] from shifted 128-bit loads.
 // ------------------------------------------------------------------------------------------
-template <int OP, int W>
-__global__ __launch_bounds__(kThreads) void slide_direct_kernel(const float *__restrict__ x,
+// STRIPS = 4: one 1024-output tile per wavefront, four wavefronts per workgroup.  STRIPS = 1: one
+// 256-output strip per wavefront and one wavefront per workgroup — the shape in which a plain copy
+// measures fastest on this GPU (6.7 against 6.1 TB/s), used for large inputs.
+template <int OP, int W, int STRIPS>
+__global__ __launch_bounds__(STRIPS == 1 ? kWave : kThreads) void slide_direct_kernel(const float *__restrict__ x,
                                                                 float *__restrict__ y, int len, int lo,
                                                                 float scale, int tiles_per_row, int64_t n_tiles,
                                                                 int remap)
 {
     using O = Op<OP>;
     constexpr int NV = (W + 2) / 4 + 1;            // float4 groups covering x[q .. q+W+2]
-    // One 1024-output tile per wavefront, tiles numbered over all rows; four consecutive tiles per
-    // workgroup (the tiles in flight then stay a compact window of memory).
-    const int64_t n_units = (n_tiles + kWavesPerWg - 1) / kWavesPerWg;
+    constexpr int WPW = STRIPS == 1 ? 1 : kWavesPerWg;     // wavefronts per workgroup
+    // Tiles numbered over all rows; consecutive tiles per workgroup (the tiles in flight then stay
+    // a compact window of memory).
+    const int64_t n_units = (n_tiles + WPW - 1) / WPW;
     const int64_t unit = remap ? xcd_unit(n_units) : (int64_t)blockIdx.x;
     if (unit < 0) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t gt = unit * kWavesPerWg + wave;
+    const int64_t gt = unit * WPW + wave;
     if (gt >= n_tiles) return;
     const int64_t r = gt / tiles_per_row;
     const int t = (int)(gt - r * tiles_per_row);
     const float *xr = x + r * (int64_t)len;
     float *yr = y + r * (int64_t)lo;
     // tile origins pulled back so that every 1 KB strip store starts on a 64-byte line of y
-    const int t0 = t * 1024 - (int)((r * lo) & 15);
+    const int t0 = t * (256 * STRIPS) - (int)((r * lo) & 15);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < STRIPS; ++j) {
         const int q = t0 + j * 256 + 4 * lane;       // first of this lane's four outputs
         if (q >= lo || q + 4 <= 0) continue;
         float a[4 * NV];
@@ -385,16 +389,31 @@ template <int OP>
 hipError_t launch_direct(const float *x, float *y, int64_t rows, int len, int lo, int w, float scale,
                          hipStream_t s)
 {
-    const int tiles_per_row = (lo + max_origin_shift(lo, 16) + 1023) / 1024;          // origins move back
+    // One strip per single-wavefront workgroup for large inputs (6.1-6.4 TB/s against 5.6 on x[32768,16384],
+    // w = 2 .. 9) and for small ones (1 M elements: 3.4 us against 4.3 us cold, 3.1 against 3.2 warm, in a
+    // graph); in between (4 M elements: 7.8 us against 8.9 us cold, but 6.3 against 4.7 us warm from the
+    // last-level cache, where the launch rate of 16 K tiny workgroups is the limit) the tiles stay.
+    // slide_chunk bit 16 forces tiles, bit 32 strips.
+    const int64_t n_out = rows * (int64_t)lo;
+    const bool fine = (n_out >= ((int64_t)1 << 24) || n_out <= ((int64_t)1 << 21) || (g_opt.slide_chunk & 32)) &&
+                      !(g_opt.slide_chunk & 16);
+    const int tile_out = fine ? 256 : 1024;
+    const int tiles_per_row = (lo + max_origin_shift(lo, 16) + tile_out - 1) / tile_out;          // origins move back
     const int64_t n_tiles = rows * tiles_per_row;
-    const int64_t n_units = (n_tiles + kWavesPerWg - 1) / kWavesPerWg;
-    const int remap = (g_opt.slide_chunk & 8) ? 0 : 1;
+    const int64_t n_units = fine ? n_tiles : (n_tiles + kWavesPerWg - 1) / kWavesPerWg;
+    // strips go out in launch order (measured equal or better than the XCD-contiguous mapping: w = 9 6.38
+    // against 6.18 TB/s); slide_chunk bit 4 forces the mapping on, bit 8 off
+    const int remap = (g_opt.slide_chunk & 8) ? 0 : ((g_opt.slide_chunk & 4) || !fine ? 1 : 0);
     const int64_t grid = remap ? xcd_grid(n_units) : n_units;
     if (grid > 2147483647LL) return hipErrorInvalidValue;
 #define SWS_DIRECT(WV)                                                                                     \
     case WV:                                                                                               \
-        hipLaunchKernelGGL((slide_direct_kernel<OP, WV>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, \
-                           len, lo, scale, tiles_per_row, n_tiles, remap);                                 \
+        if (fine)                                                                                          \
+            hipLaunchKernelGGL((slide_direct_kernel<OP, WV, 1>), dim3((unsigned)grid), dim3(kWave), 0, s, x, y, \
+                               len, lo, scale, tiles_per_row, n_tiles, remap);                             \
+        else                                                                                               \
+            hipLaunchKernelGGL((slide_direct_kernel<OP, WV, 4>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, \
+                               len, lo, scale, tiles_per_row, n_tiles, remap);                             \
         break
     switch (w) {
         SWS_DIRECT(1); SWS_DIRECT(2); SWS_DIRECT(3); SWS_DIRECT(4); SWS_DIRECT(5);
@@ -532,7 +551,9 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
         // the scan kernel) or on small problems (latency-bound: fewer phases per tile): the
         // shifted-load kernel.  Measured, max, 2 GiB: 4096-long rows 0.76 ms against 0.79-0.82;
         // 16384-long rows 0.76-0.77 against 0.73-0.76; cfg 1 in a HIP graph 3.0-3.4 us against 4.3.
-        const bool small_w = w <= kDirectMaxW && (lo <= 8192 || rows * len64 <= (8LL << 20));
+        // On large inputs its one-strip-per-wavefront form beats the scan kernel at any row length
+        // (x[32768,16384], w = 2 .. 9: 6.1-6.4 TB/s against 5.9-6.0).
+        const bool small_w = w <= kDirectMaxW && (lo <= 8192 || rows * len64 <= (8LL << 20) || rows * (int64_t)lo >= (1LL << 24));
         if (w == 1) variant = padded ? 1 : 2;
         else if (padded && pad_mode == SWS_PAD_SHRINK) variant = w <= kScanMaxW ? 3 : 1;   // one pass rescales by the real elements
         else if (padded) variant = w <= kChainMinW ? 3 : 6;   // 6: a chain over extended rows

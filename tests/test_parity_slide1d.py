@@ -317,3 +317,28 @@ def test_copy_is_bit_exact_for_every_variant_and_ragged_sizes(B, variant):
             assert torch.equal(dst[:n], src) and bool((dst[n:] == -1.0).all()), "variant %d n %d" % (variant, n)
     finally:
         B.sws_set_option("copy_variant", 0)
+
+
+@pytest.mark.parametrize("chunk", [16, 32])
+@pytest.mark.parametrize("w", [1, 2, 3, 4, 5, 7, 9])
+def test_shifted_load_kernel_in_both_shapes(B, w, chunk):
+    """The small-window kernel as 1024-output tiles (option slide_chunk bit 16) and as 256-output strips, one
+    per single-wavefront workgroup (bit 32): rows that move the output alignment, ragged tails, rows
+    shorter than a strip."""
+    B.sws_set_option("slide_variant", 2)
+    B.sws_set_option("slide_chunk", chunk)
+    try:
+        for rows, lo in ((3, 1000), (5, 255), (2, 256), (7, 257), (4, 4099), (1, 70001), (9, 3), (6, 1)):
+            r = np.random.Generator(np.random.PCG64(w * 1000 + lo + chunk))
+            x = (r.random((rows, lo + w - 1), dtype=np.float32) * 2 - 1).astype(np.float32)
+            for op in (0, 1, 2):
+                y = to_host(B.sws_slide1d(op, to_gpu(x), w, 0.5))
+                ref, mag = oracle.slide1d(op, x, w, 0.5)
+                what = "w %d rows %d lo %d op %d chunk %d" % (w, rows, lo, op, chunk)
+                if op == 0:
+                    assert_within_tol(y, ref, mag, what)
+                else:
+                    assert_bit_exact(y, ref, what)
+    finally:
+        B.sws_set_option("slide_variant", 0)
+        B.sws_set_option("slide_chunk", 0)
