@@ -4,9 +4,11 @@
 //
 //  * slide_direct_kernel: the Vector Slide idea of Section 3 (Algorithm 4) — the output
 //    vector is the (+) of w shifted copies of the input vector.  A lane owns four consecutive
-//    outputs and reads its shifted operands as 128-bit loads at +4, +8 elements.  Used for
-//    w = 1 (a scaled copy) and for w <= 9 on short rows or small problems; on long rows of
-//    large inputs the scan below is 3-6 % faster even at w = 2 (measured).
+//    outputs and reads its shifted operands as 128-bit loads at +4, +8, +12 elements.  Two launch
+//    shapes: 1024-output tiles, four wavefronts per workgroup (w <= 9 on short rows or small
+//    problems), and 256-output strips, one wavefront per workgroup (w <= 11 on large inputs, where
+//    it beats the scan below by 3-6 %; in the tile shape the scan is the faster one there).
+//    Also w = 1 (a scaled copy).
 //
 //  * slide_scan_kernel (every w >= 2): the block form of the Vector Input algorithm
 //    (Section 3, Algorithm 2).  A wavefront owns a tile of 64*C consecutive inputs cut
@@ -418,6 +420,7 @@ hipError_t launch_direct(const float *x, float *y, int64_t rows, int len, int lo
     switch (w) {
         SWS_DIRECT(1); SWS_DIRECT(2); SWS_DIRECT(3); SWS_DIRECT(4); SWS_DIRECT(5);
         SWS_DIRECT(6); SWS_DIRECT(7); SWS_DIRECT(8); SWS_DIRECT(9);
+        SWS_DIRECT(10); SWS_DIRECT(11);
     default: return hipErrorInvalidValue;
     }
 #undef SWS_DIRECT
@@ -528,7 +531,7 @@ hipError_t launch_chain_padded(const float *x, float *y, int64_t rows, int len, 
     return hipSuccess;
 }
 
-constexpr int kDirectMaxW = 9;
+constexpr int kDirectMaxW = 11;                      // widest window of the shifted-load kernel (four 128-bit loads per lane)
 constexpr int kScanMaxW = kWave * 16 - 64 + 1;      // leaves at least 64 outputs per wave tile
 constexpr int kChainMinW = 850;                     // longer windows run as a chain of shorter ones
 
@@ -553,7 +556,10 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
         // 16384-long rows 0.76-0.77 against 0.73-0.76; cfg 1 in a HIP graph 3.0-3.4 us against 4.3.
         // On large inputs its one-strip-per-wavefront form beats the scan kernel at any row length
         // (x[32768,16384], w = 2 .. 9: 6.1-6.4 TB/s against 5.9-6.0).
-        const bool small_w = w <= kDirectMaxW && (lo <= 8192 || rows * len64 <= (8LL << 20) || rows * (int64_t)lo >= (1LL << 24));
+        // (Strips against the scan kernel there, TB/s: w = 10 6.07 / 5.85, w = 12 6.01 / 5.96, w = 16 4.7 / 5.96 —
+        // beyond four 128-bit loads per lane the re-reads through L1 cost more than the scan's LDS passes.)
+        const bool small_w = (w <= 9 && (lo <= 8192 || rows * len64 <= (8LL << 20))) ||
+                             (w <= kDirectMaxW && rows * (int64_t)lo >= (1LL << 24));
         if (w == 1) variant = padded ? 1 : 2;
         else if (padded && pad_mode == SWS_PAD_SHRINK) variant = w <= kScanMaxW ? 3 : 1;   // one pass rescales by the real elements
         else if (padded) variant = w <= kChainMinW ? 3 : 6;   // 6: a chain over extended rows

@@ -320,7 +320,7 @@ def test_copy_is_bit_exact_for_every_variant_and_ragged_sizes(B, variant):
 
 
 @pytest.mark.parametrize("chunk", [16, 32])
-@pytest.mark.parametrize("w", [1, 2, 3, 4, 5, 7, 9])
+@pytest.mark.parametrize("w", [1, 2, 3, 4, 5, 7, 9, 10, 11])
 def test_shifted_load_kernel_in_both_shapes(B, w, chunk):
     """The small-window kernel as 1024-output tiles (option slide_chunk bit 16) and as 256-output strips, one
     per single-wavefront workgroup (bit 32): rows that move the output alignment, ragged tails, rows
