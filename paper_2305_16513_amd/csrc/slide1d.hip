@@ -456,8 +456,11 @@ hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, 
     // is best while the halo is small; with a large halo two tiles per wavefront and plain
     // round-robin placement of workgroups over the XCDs win.
     const int64_t n_tiles = rows * tiles;
-    int64_t g = (S <= 64) ? kWavesPerWg : 2 * kWavesPerWg;
-    bool remap = S <= 64;
+    // (For + the first form stays ahead up to w = 170 — x[32768,16384], w = 80 .. 160: 5.98-6.08 TB/s
+    // against 5.5-5.7 — while max / min already prefer the second from w = 80 on: 5.7-5.94 against 5.6-5.85.)
+    const bool one_tile = S <= 64 || (OP == SWS_OP_ADD && S <= 172);
+    int64_t g = one_tile ? kWavesPerWg : 2 * kWavesPerWg;
+    bool remap = one_tile;
     if (g_opt.slide_group > 0) g = (g_opt.slide_group + kWavesPerWg - 1) / kWavesPerWg * kWavesPerWg;
     if (opt & 4) remap = true;
     if (opt & 8) remap = false;
