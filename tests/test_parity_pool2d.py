@@ -171,7 +171,7 @@ def test_pool2d_ex_equal_pads_match_pool2d_and_argument_checks(B):
 
 def test_more_than_2_to_the_32_elements(B):
     """349 952 planes of 112 x 112 (4.4e9 elements): plane offsets beyond 2^32 elements, for the
-    specialised band kernel, the run-time separable kernel and the max-pooling adjoint."""
+    specialised band kernel, the run-time separable kernel and the two pooling adjoints."""
     import torch
     planes = 349952                                                       # 5468 x 64
     free, _ = torch.cuda.mem_get_info()
@@ -195,5 +195,8 @@ def test_more_than_2_to_the_32_elements(B):
     ref = oracle.maxpool2d_grad(xs, gys, 3, 3, 2, 2, 1, 1)
     mag = oracle.maxpool2d_grad(xs, np.abs(gys), 3, 3, 2, 2, 1, 1)
     assert_within_tol(to_host(gx.view(planes, 112, 112)[sample]).reshape(ref.shape), ref, mag, "big max pool adjoint")
+    B.sws_avgpool2d_grad(gy, 112, 112, 3, 3, 2, 2, 1, 1, B.SWS_DIV_REAL_CELLS, 1.0, gx=gx)
+    ref, mag = oracle.avgpool2d_grad(gys, 112, 112, 3, 3, 2, 2, 1, 1, True, 1.0)
+    assert_within_tol(to_host(gx.view(planes, 112, 112)[sample]).reshape(ref.shape), ref, mag, "big average pool adjoint")
     del x, gy, gx
     torch.cuda.empty_cache()
