@@ -640,6 +640,14 @@ hipError_t launch_conv2d_grad_weight(const float *x, const float *gy, float *gw,
         GwGeom gm;
         gm.Cin = (int)Cin; gm.Cout = (int)Cout; gm.L = (int)W; gm.Lo = (int)Wo; gm.k = kw; gm.pad = pw; gm.dilation = 1;
         gm.H = (int)H; gm.Ho = (int)Ho; gm.kh = kh; gm.sh = sh; gm.ph = ph; gm.sw = sw; gm.x_cs = H * W; gm.gy_cs = Ho * Wo;
+        if (kh == 1 && kw == 1 && sh == 1 && sw == 1 && ph == 0 && pw == 0 && H > 1) {
+            // a 1 x 1 kernel does not see the rows: the plane may be taken as one long row, if that fills the
+            // 64-position slabs better than whole rows (or several short rows packed into one) do
+            const int64_t hw = H * W;
+            const double flat = (double)hw / (double)((hw + 63) / 64 * 64);
+            const double rows = W >= 64 ? (double)W / (double)((W + 63) / 64 * 64) : (double)((64 / W) * W) / 64.0;
+            if (flat > rows) { gm.L = gm.Lo = (int)hw; gm.H = gm.Ho = 1; }
+        }
         bool taken = false;
         const hipError_t e = launch_dense_gw_taps(x, gy, gw, N, gm, s, &taken);
         if (taken || e != hipSuccess) return e;
