@@ -3,11 +3,15 @@
 //  * with respect to the input: at stride 1 the adjoint is itself a sliding dot product — over
 //    the output gradients, taps last first, channels swapped inside each group, padding
 //    span - 1 - pad — so it runs on the forward kernels, which read the weight array through
-//    that view (no transformed copy is made).  Other cases: one thread per input element.
+//    that view (no transformed copy is made).  At larger strides (dense channels) the cells of gx
+//    fall into stride-many phases, each reached by every stride-th tap only: one stride-1 launch
+//    of the matrix-core kernel per phase, stored with the stride.  Other cases: one thread per
+//    input element.
 //
 //  * with respect to the weights: gw[co,ci,t] = sum over images and positions of
 //    gy[b,co,i] * x[b,ci,i*stride + t*dilation - pad], a reduction over everything the forward
-//    pass slides over.  Two tuned kernels (stride 1):
+//    pass slides over.  Two tuned kernels (thin: stride 1; dense: stride 1 or 2 along the row,
+//    any stride between rows, short rows packed several to a slab):
 //      - thin (one input channel per output channel): a wavefront stages a tile of x and of gy
 //        in LDS, a lane keeps 16 gradients and its window of x in registers and adds
 //        gy[e] * x[e+t] into one accumulator per tap; tiles of the same channel follow each other,
