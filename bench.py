@@ -270,7 +270,7 @@ def sweeps_table(torch, B, workloads, iters=20):
     for dt, dn in ((torch.bfloat16, "bf16"), (torch.float16, "f16")):
         xs = x16 if dt == torch.bfloat16 else x16.to(dt)
         for op, opn in ((0, "add"), (1, "max")):
-            for w in WINDOWS5 if dn == "bf16" else (64,):
+            for w in (3, 9) + tuple(WINDOWS5) if dn == "bf16" else (64,):
                 y = torch.empty(256, 128, LEN5 - w + 1, device="cuda", dtype=dt)
                 ms = time_launches(torch, lambda: B.sws_slide1d_16(op, xs, w, 1.0 / w, y=y), iters)
                 nb = slide_bytes(ROWS5, LEN5, w) // 2

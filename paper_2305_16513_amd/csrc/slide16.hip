@@ -10,6 +10,9 @@
 // element the kernel is bound by instruction issue and latency rather than by HBM, hence the wide
 // strips (half as many staging and combine steps per element as the fp32 kernel's four-element
 // strips) and the software prefetch of the next tile.
+// Windows up to 33 also have a kernel on shifted loads (eight outputs per lane straight from
+// 128-bit loads, no LDS); it serves the windows up to 9 everywhere, and the others on short rows
+// and small tensors, where 1024-element wave tiles fit badly.
 // Plain rows only (no boundary rules, no chains of windows).
 #include "sws_internal.h"
 
@@ -267,7 +270,7 @@ __global__ __launch_bounds__(kThreads) void slide16_scan_kernel(const T *__restr
     }
 }
 
-// Direct evaluation (w = 1 and windows beyond the scan kernel's reach): one thread per output,
+// Direct evaluation (windows beyond the scan kernel's reach): one thread per output,
 // fp32 accumulation left to right, one rounding at the end.
 template <int OP, typename T>
 __global__ __launch_bounds__(kThreads) void slide16_naive_kernel(const T *__restrict__ x, T *__restrict__ y,
@@ -285,12 +288,144 @@ __global__ __launch_bounds__(kThreads) void slide16_naive_kernel(const T *__rest
     }
 }
 
+// Small windows on shifted loads: a lane owns eight consecutive outputs and reads the w + 7 inputs
+// under them as 128-bit loads.  Up to w = 8 each output combines its inputs left to right (Eq. 3 as
+// written).  From w = 9 the eight windows share the inputs 7 .. w-1 of the strip: that core is
+// combined once, and output c adds the suffix c .. 6 in front of it and the prefix w .. w+c-1
+// behind it (running sums, the register-level form of Section 3's prefix / suffix split), about
+// w + 20 operations for the eight outputs instead of 8 (w - 1).  All of it in fp32, one rounding.
+// Workgroups are one wavefront and short-lived (512 outputs of a row, or several short rows side
+// by side), which streams better than long-lived tiles.
+// A 128-bit load may run past the end of its row (those values reach no valid output) but not
+// past the ends of x: there it is replaced by element loads.
+template <int OP, typename T, int W>
+__global__ __launch_bounds__(kWave) void slide16_direct_kernel(const T *__restrict__ x, T *__restrict__ y,
+                                                               int64_t rows, int len, int lo, float scale,
+                                                               int strips, int wg_per_row, int rows_per_wg, int recip,
+                                                               int align)
+{
+    using O = Op<OP>;
+    using IO = Io<T>;
+    constexpr int NL = (W + 7 + 7) / 8;              // 128-bit loads per strip
+    const int lane = threadIdx.x;
+    int64_t r;
+    int sidx;
+    if (rows_per_wg == 1) {
+        const int br = blockIdx.x / (unsigned)wg_per_row;
+        r = br;
+        sidx = (blockIdx.x - br * wg_per_row) * kWave + lane;
+    } else {
+        const int lr = (lane * recip) >> 16;         // lane / strips, exact for lane < 64
+        if (lr >= rows_per_wg) return;
+        r = (int64_t)blockIdx.x * rows_per_wg + lr;
+        sidx = lane - lr * strips;
+    }
+    if (r >= rows || sidx >= strips) return;
+    // long rows: strips sit on the 16-byte boundaries of y, so a row that starts between two
+    // boundaries has a partial first strip (short rows would spend too many lanes on those)
+    T *yrow = y + r * (int64_t)lo;
+    const int q = 8 * sidx - (align ? (int)(((uintptr_t)yrow >> 1) & 7) : 0);
+    if (q >= lo) return;
+    const int64_t g = r * (int64_t)len + q;          // the strip's first input in x
+    const int64_t total = rows * (int64_t)len;
+    const T *xr = x + g;
+    float v[8 * NL];
+#pragma unroll
+    for (int k = 0; k < NL; ++k) {
+        if (g + 8 * k >= 0 && g + 8 * k + 8 <= total) {
+            const v8f a = IO::load8(xr + 8 * k);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) v[8 * k + c] = a[c];
+        } else {
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                const int64_t e = g + 8 * k + c;
+                v[8 * k + c] = (e >= 0 && e < total) ? IO::load1(xr + 8 * k + c) : 0.0f;
+            }
+        }
+    }
+    v8f o;
+    if constexpr (W <= 8) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            float acc = v[c];
+#pragma unroll
+            for (int j = 1; j < W; ++j) acc = O::f(acc, v[c + j]);
+            o[c] = acc;
+        }
+    } else {
+        float core = v[7];
+#pragma unroll
+        for (int j = 8; j < W; ++j) core = O::f(core, v[j]);
+        float suf[7], pre[8];
+        suf[6] = v[6];
+#pragma unroll
+        for (int c = 5; c >= 0; --c) suf[c] = O::f(v[c], suf[c + 1]);
+        pre[1] = v[W];
+#pragma unroll
+        for (int c = 2; c < 8; ++c) pre[c] = O::f(pre[c - 1], v[W + c - 1]);
+        o[0] = O::f(suf[0], core);
+        o[7] = O::f(core, pre[7]);
+#pragma unroll
+        for (int c = 1; c < 7; ++c) o[c] = O::f(O::f(suf[c], core), pre[c]);
+    }
+    if (OP == SWS_OP_ADD) o *= scale;
+    T *yr = yrow + q;
+    if (q >= 0 && q + 8 <= lo) {
+        IO::store8(yr, o);
+    } else {
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+            if (q + c >= 0 && q + c < lo) IO::store1(yr + c, o[c]);
+    }
+}
+
+constexpr int kDirectMaxW = 33;                      // five 128-bit loads per strip of eight outputs
+
+template <int OP, typename T, int W>
+hipError_t launch_16_direct_w(const T *x, T *y, int64_t rows, int len, int lo, float scale, hipStream_t s)
+{
+    // aligned strips pay from about a thousand outputs per row (measured: 4.5 against 4.3 TB/s at
+    // 4096, 2.7 against 3.7 at 224); rows of y that all start on a boundary need no shift
+    const int align = lo >= 1024 && !(lo % 8 == 0 && (uintptr_t)y % 16 == 0);
+    const int strips = (lo + (align ? 14 : 7)) / 8;
+    const int wg_per_row = (strips + kWave - 1) / kWave;
+    const int rows_per_wg = strips < kWave ? kWave / strips : 1;
+    const int recip = 65536 / strips + 1;
+    const int64_t grid = rows_per_wg == 1 ? rows * wg_per_row : (rows + rows_per_wg - 1) / rows_per_wg;
+    if (grid > 2147483647LL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((slide16_direct_kernel<OP, T, W>), dim3((unsigned)grid), dim3(kWave), 0, s, x, y, rows, len, lo,
+                       scale, strips, wg_per_row, rows_per_wg, recip, align);
+    return hipGetLastError();
+}
+
+template <int OP, typename T, int W0>
+hipError_t launch_16_direct(const T *x, T *y, int64_t rows, int len, int lo, int w, float scale, hipStream_t s)
+{
+    if constexpr (W0 > kDirectMaxW) {
+        return hipErrorInvalidValue;
+    } else {
+        if (w == W0) return launch_16_direct_w<OP, T, W0>(x, y, rows, len, lo, scale, s);
+        return launch_16_direct<OP, T, W0 + 1>(x, y, rows, len, lo, w, scale, s);
+    }
+}
+
 constexpr int kScanMaxW = kN - 64 + 1;               // leaves at least 64 outputs per wave tile
 
 template <int OP, typename T>
 hipError_t launch_16(const T *x, T *y, int64_t rows, int len, int lo, int w, float scale, hipStream_t s)
 {
-    if (w >= 2 && w <= kScanMaxW && g_opt.slide_variant != 1) {
+    const int variant = g_opt.slide_variant;
+    // Measured on bf16: up to w = 9 (two loads per strip) the shifted loads win at every size (5.2 to
+    // 5.8 TB/s against the scan's 4.9 to 5.1 on a 1 GB tensor); beyond that they win where the scan
+    // kernel's 1024-element wave tiles fit badly: rows under 2048 outputs (3 to 25 times faster at
+    // 56 to 224 elements per row) and tensors under 2^25 elements (2 to 5 times).
+    const bool direct_auto = w <= 9 || lo < 2048 || rows * (int64_t)len <= (1LL << 25);
+    if (w <= kDirectMaxW && variant != 1 && (variant == 3 || w == 1 || (variant != 2 && direct_auto))) {
+        const hipError_t e = launch_16_direct<OP, T, 1>(x, y, rows, len, lo, w, scale, s);
+        if (e != hipErrorInvalidValue) return e;     // a grid beyond the launch limit: the kernels below
+    }
+    if (w >= 2 && w <= kScanMaxW && variant != 1) {
         const int S = w - 1;
         const int tout = (kN - S) & ~(kLine - 1);    // a multiple of 64 bytes of y (at least 64 outputs)
         const int tiles = (lo + max_origin_shift(lo, kLine) + tout - 1) / tout;
@@ -299,6 +434,9 @@ hipError_t launch_16(const T *x, T *y, int64_t rows, int len, int lo, int w, flo
         // worked on; workgroups in launch order
         int64_t g = 16 * kWavesPerWg;
         int remap = 0;
+        // ... halved while that leaves fewer than 2048 workgroups (measured on 64 rows of 2^20:
+        // 5.8 against 4.9 TB/s; a limit of 4096 loses again on 4096 x 4096)
+        while (g > kWavesPerWg && n_tiles / g < 2048) g /= 2;
         if (g_opt.slide_group > 0) g = (g_opt.slide_group + kWavesPerWg - 1) / kWavesPerWg * kWavesPerWg;
         if (g_opt.slide_chunk & 4) remap = 1;
         if (g_opt.slide_chunk & 8) remap = 0;

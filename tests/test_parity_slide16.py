@@ -94,6 +94,46 @@ def test_add_is_exact_on_small_integers(B, kind):
         assert np.array_equal(y, ref)
 
 
+@pytest.mark.parametrize("kind", ["bf16", "f16"])
+@pytest.mark.parametrize("w", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 15, 16, 17, 18, 24, 25, 26, 31, 32, 33, 34])
+@pytest.mark.parametrize("rows,length", [(3, 5003), (300, 56), (1000, 9), (5, 520), (2, 1031), (40, 512 + 8), (17, 24)])
+def test_small_windows_on_both_kernels(B, kind, w, rows, length):
+    """Windows up to 33 have two kernels (shifted loads; the scan).  Both are forced in turn, with x
+    and y starting 2 bytes past a 16-byte boundary as well, so that the strips' alignment to y is
+    exercised for every phase; memory around y must stay untouched."""
+    if w > length:
+        pytest.skip("window longer than the row")
+    tdt, odt, half_step = TYPES[kind]
+    rng = np.random.Generator(np.random.PCG64(77 * w + length))
+    x32 = (rng.random((rows, length), dtype=np.float32) * 2 - 1).astype(np.float32)
+    xq = torch.from_numpy(x32).to(tdt)
+    xw = xq.to(torch.float32).numpy()
+    lo = length - w + 1
+    try:
+        for variant in (2, 3):
+            B.sws_set_option("slide_variant", variant)
+            for shift in (0, 1, 5):
+                xbuf = torch.zeros(rows * length + 8, dtype=tdt, device="cuda")
+                xs = xbuf[shift:shift + rows * length].view(rows, length)
+                xs.copy_(xq)
+                ybuf = torch.full((rows * lo + 16,), 7.0, dtype=tdt, device="cuda")
+                ys = ybuf[shift:shift + rows * lo].view(rows, lo)
+                for op in ("add", "max", "min"):
+                    B.sws_slide1d_16(OPS[op], xs, w, 1.0, y=ys)
+                    got = ys.cpu().to(torch.float64).numpy()
+                    ref, mag = oracle.slide1d(OPS[op], xw, w, 1.0)
+                    what = "%s %s w=%d %dx%d variant %d shift %d" % (kind, op, w, rows, length, variant, shift)
+                    if op != "add":
+                        assert np.array_equal(got, ref), what
+                    else:
+                        allowed = TOL * mag + (np.abs(ref) + TOL * mag) * half_step + (2.0 ** -25 if kind == "f16" else 0.0)
+                        assert (np.abs(got - ref) <= allowed).all(), what
+                    guard = ybuf.cpu().to(torch.float32)
+                    assert (guard[:shift] == 7.0).all() and (guard[shift + rows * lo:] == 7.0).all(), what
+    finally:
+        B.sws_set_option("slide_variant", 0)
+
+
 def test_argument_checks(B):
     x = torch.zeros((2, 100), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(B.SwsError):
