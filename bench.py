@@ -193,7 +193,7 @@ def sweeps_table(torch, B, workloads, iters=20):
     2*k FLOP per output; the vector-ALU peak without packed fp32 is 78.6 TFLOP/s."""
     g = lambda a: torch.from_numpy(a).cuda()
     out = {"filter_sweep": {}, "dilated_single": {}, "dilated_batched": {}, "pair_operator": {}, "same_size_pooling": {},
-           "storage_16bit": {}, "adjoints": {}}
+           "storage_16bit": {}, "short_rows": {}, "adjoints": {}}
     c6 = workloads.CONFIGS[6]
     rows, length = c6.x_shape[0], c6.x_shape[2]
     x6 = g(workloads.make(6)[0])
@@ -291,6 +291,23 @@ def sweeps_table(torch, B, workloads, iters=20):
                 "us": round(ms * 1e3, 2), "GBps": round(nb / ms / 1e6, 1), "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
         del y
     del x3
+    torch.cuda.empty_cache()
+    # rows far shorter than a wave tile (the rows of configuration 3's and 4's planes as a 1-D problem)
+    for rows, ln in ((262144, 56), (65536, 224)):
+        xs = g(workloads.make(5, x_shape=(rows, ln), wgt_shape=(1, 1, 1))[0])
+        for dt, dn in ((torch.float32, "f32"), (torch.bfloat16, "bf16")):
+            xd = xs.to(dt)
+            for w in (3, 16):
+                y = torch.empty(rows, ln - w + 1, device="cuda", dtype=dt)
+                fn = (lambda: B.sws_slide1d(1, xd, w, 1.0, y=y)) if dt == torch.float32 else \
+                     (lambda: B.sws_slide1d_16(1, xd, w, 1.0, y=y))
+                ms = time_launches(torch, fn, iters)
+                nb = xd.element_size() * rows * (2 * ln - w + 1)
+                out["short_rows"]["%s_max_w%d_%dx%d" % (dn, w, rows, ln)] = {
+                    "us": round(ms * 1e3, 2), "GBps": round(nb / ms / 1e6, 1), "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+                del y
+            del xd
+        del xs
     torch.cuda.empty_cache()
     # the adjoints of the sliding dot product (training): configuration 5's depthwise layer (HBM-bound:
     # grad-input moves what the forward pass moves, grad-weight reads x and gy) and configuration 2's

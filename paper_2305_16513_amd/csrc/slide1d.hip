@@ -1,6 +1,7 @@
 // sws_slide1d — sliding window sums over rows (Section 2.2, Eq. 3) for gfx950.
 //
-// Two tuned kernels plus the direct-evaluation fallback:
+// Two tuned kernels plus the direct-evaluation fallback (rows of a few hundred elements with
+// windows up to 33 go to a third, slide_rows.hip, which packs several rows into a wavefront):
 //
 //  * slide_direct_kernel: the Vector Slide idea of Section 3 (Algorithm 4) — the output
 //    vector is the (+) of w shifted copies of the input vector.  A lane owns four consecutive
@@ -550,6 +551,7 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
     if (variant == 2 && w > kDirectMaxW) variant = 0;
     if (variant == 3 && (w < 2 || w > kScanMaxW)) variant = 0;
     if (variant == 4) return launch_slide1d_generic(op, x, y, rows, len64, w, scale, s);   // generic-operator kernel (A/B)
+    if (variant == 7 && (padded || w > slide1d_rows_max_w())) variant = 0;
     // Measured on 16384-long rows: beyond w = 850 two links of half the width beat one pass whose
     // tiles are mostly halo.
     if (variant == 0) {
@@ -563,7 +565,15 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
         // beyond four 128-bit loads per lane the re-reads through L1 cost more than the scan's LDS passes.)
         const bool small_w = (w <= 9 && (lo <= 8192 || rows * len64 <= (8LL << 20))) ||
                              (w <= kDirectMaxW && rows * (int64_t)lo >= (1LL << 24));
-        if (w == 1) variant = padded ? 1 : 2;
+        // Rows too short for either: up to 256 outputs (one strip of the shifted-load kernel, a
+        // quarter of the scan's wave tile) the short-row kernel for every window it has, several
+        // rows per wavefront; up to 1024 outputs for the windows the shifted loads do not take.
+        // Measured, max, TB/s, short-row kernel against the above: 262144 rows of 56 5.4-6.7 / 0.4-2.8;
+        // 65536 x 224 5.4-6.7 / 5.2-6.0 (w <= 9), 1.9 (w >= 12); 32768 x 512 5.3-6.2 / 6.3-6.6 (w <= 9),
+        // 5.8-6.5 / 3.5-4.3 (w >= 12); 16384 x 1024 5.9-6.3 / 3.7-6.2 (w >= 12); from 2048 no gain.
+        const bool short_rows = !padded && w <= slide1d_rows_max_w() && (lo <= 256 || (w > 9 && lo <= 1024));
+        if (short_rows) variant = 7;
+        else if (w == 1) variant = padded ? 1 : 2;
         else if (padded && pad_mode == SWS_PAD_SHRINK) variant = w <= kScanMaxW ? 3 : 1;   // one pass rescales by the real elements
         else if (padded) variant = w <= kChainMinW ? 3 : 6;   // 6: a chain over extended rows
         else if (small_w) variant = 2;
@@ -583,6 +593,11 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
         case SWS_OP_MAX: return launch_chain_padded<SWS_OP_MAX>(x, y, rows, len, lo, w, pad_left, pad_mode, scale, s);
         default: return launch_chain_padded<SWS_OP_MIN>(x, y, rows, len, lo, w, pad_left, pad_mode, scale, s);
         }
+    }
+    if (variant == 7) {
+        const hipError_t e = launch_slide1d_rows(op, x, y, rows, len, lo, w, scale, s);
+        if (e != hipErrorInvalidValue) return e;
+        variant = w == 1 ? 2 : 3;                    // a grid beyond the launch limit
     }
     if (variant == 1) return launch_slide1d_naive(op, x, y, rows, len64, w, pad_left, pad_right, pad_mode, scale, s);
     if (variant == 2) {

@@ -87,6 +87,11 @@ hipError_t launch_slide1d_16(int op, int dtype, const void *x, void *y, int64_t 
 // Generic-operator kernels (slide_generic.hip): the pair operator, and +, max, min as a cross-check.
 hipError_t launch_slide1d_pair(const float *u, const float *v, float *yu, float *yv, int64_t rows, int64_t len,
                                int32_t w, hipStream_t s);
+// Short rows, windows up to slide1d_rows_max_w(): four outputs per lane from shifted 128-bit loads,
+// several rows per wavefront.  hipErrorInvalidValue: not taken (w or grid beyond its reach).
+int slide1d_rows_max_w();
+hipError_t launch_slide1d_rows(int op, const float *x, float *y, int64_t rows, int len, int lo, int32_t w, float scale,
+                               hipStream_t s);
 hipError_t launch_slide1d_generic(int op, const float *x, float *y, int64_t rows, int64_t len, int32_t w, float scale,
                                   hipStream_t s);
 hipError_t launch_pool2d(int op, const float *x, float *y, int64_t planes, int64_t H, int64_t W,

@@ -342,3 +342,40 @@ def test_shifted_load_kernel_in_both_shapes(B, w, chunk):
     finally:
         B.sws_set_option("slide_variant", 0)
         B.sws_set_option("slide_chunk", 0)
+
+
+@pytest.mark.parametrize("variant", [0, 7])
+@pytest.mark.parametrize("w", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 12, 13, 16, 17, 21, 25, 29, 32, 33, 34])
+def test_short_row_kernel(B, w, variant):
+    """Windows up to 33 on short rows: four outputs per lane, several rows per wavefront.  Forced
+    (option slide_variant 7, also on rows longer than it is chosen for) and as the library chooses;
+    x and y start off the 16-byte boundaries, and the elements around y must stay untouched."""
+    import torch
+    B.sws_set_option("slide_variant", variant)
+    try:
+        for rows, length in ((7, 56), (300, 57), (1000, 9), (40, 260), (2, 4), (5, 1031), (3, 5003), (130, 224),
+                             (65, 1), (64, 64), (9, 255 + w), (9, 256 + w)):
+            if w > length:
+                continue
+            lo = length - w + 1
+            r = np.random.Generator(np.random.PCG64(w * 977 + length))
+            x = (r.random((rows, length), dtype=np.float32) * 2 - 1).astype(np.float32)
+            xbuf = torch.zeros(rows * length + 8, device="cuda")
+            xs = xbuf[1:1 + rows * length].view(rows, length)
+            xs.copy_(torch.from_numpy(x))
+            for op in (0, 1, 2):
+                ybuf = torch.full((rows * lo + 8,), 7.0, device="cuda")
+                ys = ybuf[3:3 + rows * lo].view(rows, lo)
+                B.sws_slide1d(op, xs, w, 0.5, y=ys)
+                y = to_host(ys)
+                ref, mag = oracle.slide1d(op, x, w, 0.5)
+                what = "w %d rows %d len %d op %d variant %d" % (w, rows, length, op, variant)
+                if op == 0:
+                    assert_within_tol(y, ref, mag, what)
+                else:
+                    assert_bit_exact(y, ref, what)
+                guard = ybuf.cpu()
+                assert (guard[:3] == 7.0).all() and (guard[3 + rows * lo:] == 7.0).all(), what
+    finally:
+        B.sws_set_option("slide_variant", 0)
+
