@@ -432,6 +432,15 @@ def run_only(torch, B, workloads, name, steps):
         else:
             gw = torch.empty_like(w4)
             fn = lambda: B.sws_conv2d_grad_weight(x4, gy, 3, 3, 1, 1, 1, 1, gw=gw)
+    elif name.startswith("short_rows_"):                  # short_rows_<f32|bf16>_<add|max>_w<w>_<rows>x<len>
+        _, _, dn, opn, wn, shp = name.split("_")
+        w = int(wn[1:])
+        rows, ln = (int(v) for v in shp.split("x"))
+        dt = {"f32": torch.float32, "bf16": torch.bfloat16}[dn]
+        xd = g(workloads.make(5, x_shape=(rows, ln), wgt_shape=(1, 1, 1))[0]).to(dt)
+        y = torch.empty(rows, ln - w + 1, device="cuda", dtype=dt)
+        op = 0 if opn == "add" else 1
+        fn = (lambda: B.sws_slide1d(op, xd, w, 1.0, y=y)) if dn == "f32" else (lambda: B.sws_slide1d_16(op, xd, w, 1.0, y=y))
     elif name.startswith("slide16_"):                     # slide16_<bf16|f16>_<add|max>_w<w>
         _, dn, opn, wn = name.split("_")
         w = int(wn[1:])
