@@ -551,7 +551,7 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
     if (variant == 2 && w > kDirectMaxW) variant = 0;
     if (variant == 3 && (w < 2 || w > kScanMaxW)) variant = 0;
     if (variant == 4) return launch_slide1d_generic(op, x, y, rows, len64, w, scale, s);   // generic-operator kernel (A/B)
-    if (variant == 7 && (padded || w > slide1d_rows_max_w())) variant = 0;
+    if (variant == 7 && w > slide1d_rows_max_w()) variant = 0;
     // Measured on 16384-long rows: beyond w = 850 two links of half the width beat one pass whose
     // tiles are mostly halo.
     if (variant == 0) {
@@ -571,7 +571,13 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
         // Measured, max, TB/s, short-row kernel against the above: 262144 rows of 56 5.4-6.7 / 0.4-2.8;
         // 65536 x 224 5.4-6.7 / 5.2-6.0 (w <= 9), 1.9 (w >= 12); 32768 x 512 5.3-6.2 / 6.3-6.6 (w <= 9),
         // 5.8-6.5 / 3.5-4.3 (w >= 12); 16384 x 1024 5.9-6.3 / 3.7-6.2 (w >= 12); from 2048 no gain.
-        const bool short_rows = !padded && w <= slide1d_rows_max_w() && (lo <= 256 || (w > 9 && lo <= 1024));
+        // With a boundary rule the alternative is the scan kernel alone and the border strips cost
+        // more as w grows (mirror, max, TB/s, short-row kernel / scan): rows of 56 5.5-1.4 / 0.4 for
+        // w = 3 .. 33; 224 5.6-2.4 / 1.6 up to w = 16, 1.4 / 1.6 at 33; 1024 5.8-3.9 / 3.5 up to 16;
+        // 2048 5.7-5.4 / 4.8-4.6 up to 9, 3.8 / 4.6 at 16.
+        const bool short_rows = w <= slide1d_rows_max_w() &&
+                                (padded ? (lo <= 128 || (w <= 16 && lo <= 1024) || (w <= 9 && lo <= 2048))
+                                        : (lo <= 256 || (w > 9 && lo <= 1024)));
         if (short_rows) variant = 7;
         else if (w == 1) variant = padded ? 1 : 2;
         else if (padded && pad_mode == SWS_PAD_SHRINK) variant = w <= kScanMaxW ? 3 : 1;   // one pass rescales by the real elements
@@ -595,9 +601,9 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
         }
     }
     if (variant == 7) {
-        const hipError_t e = launch_slide1d_rows(op, x, y, rows, len, lo, w, scale, s);
+        const hipError_t e = launch_slide1d_rows(op, x, y, rows, len, lo, w, scale, padded, pad_left, pad_mode, s);
         if (e != hipErrorInvalidValue) return e;
-        variant = w == 1 ? 2 : 3;                    // a grid beyond the launch limit
+        variant = w == 1 ? (padded ? 1 : 2) : 3;     // a grid beyond the launch limit
     }
     if (variant == 1) return launch_slide1d_naive(op, x, y, rows, len64, w, pad_left, pad_right, pad_mode, scale, s);
     if (variant == 2) {

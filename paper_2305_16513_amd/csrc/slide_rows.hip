@@ -9,7 +9,8 @@
 // front of it and the prefix w .. w+c-1 behind it (running sums: the register-level form of Section
 // 3's prefix / suffix split), about w + 6 operations for the four outputs instead of 4 (w - 1).
 // A 128-bit load may run past the end of its row (those values reach no valid output) but not past
-// the ends of x: there it is replaced by element loads.
+// the ends of x: there it is replaced by element loads.  Rows extended by a boundary rule
+// (sws_slide1d_padded) take the same path with the border strips read through the rule.
 #include "sws_internal.h"
 
 namespace sws {
@@ -21,10 +22,15 @@ typedef v4f v4f_u __attribute__((aligned(4)));
 
 constexpr int kRowsMaxW = 33;                        // nine 128-bit loads per strip of four outputs
 
-template <int OP, int W>
+// PAD: rows extended by a boundary rule (pad_left virtual elements in front; lo counts the outputs
+// of the extended row).  Loads that lie inside the physical row stay 128-bit; the others go element
+// by element through the rule.  (Two variants measured slower for w >= 16: one test per strip with
+// all-vector loads for strips clear of the borders, and border strips gathered unconditionally.)
+template <int OP, int W, bool PAD>
 __global__ __launch_bounds__(kWave) void slide_rows_kernel(const float *__restrict__ x, float *__restrict__ y,
                                                            int64_t rows, int len, int lo, float scale, int strips,
-                                                           int wg_per_row, int rows_per_wg, int recip)
+                                                           int wg_per_row, int rows_per_wg, int recip, int pad_left,
+                                                           int pad_mode)
 {
     using O = Op<OP>;
     constexpr int NL = (W + 3 + 3) / 4;              // 128-bit loads per strip
@@ -43,18 +49,38 @@ __global__ __launch_bounds__(kWave) void slide_rows_kernel(const float *__restri
     }
     if (r >= rows || sidx >= strips) return;
     const int q = 4 * sidx;                          // first of this lane's four outputs
-    const int64_t g = r * (int64_t)len + q;          // the strip's first input in x
-    const int64_t total = rows * (int64_t)len;
-    const float *xr = x + g;
     float v[4 * NL];
+    if constexpr (PAD) {
+        const float *xrow = x + r * (int64_t)len;
+        const int lv = lo + W - 1;                   // length of the extended row
 #pragma unroll
-    for (int k = 0; k < NL; ++k) {
-        if (g + 4 * k + 4 <= total) {
-            const v4f a = *(const v4f_u *)(xr + 4 * k);
-            v[4 * k] = a.x; v[4 * k + 1] = a.y; v[4 * k + 2] = a.z; v[4 * k + 3] = a.w;
-        } else {
+        for (int k = 0; k < NL; ++k) {
+            const int p0 = q + 4 * k - pad_left;     // physical position of the load's first element
+            if (p0 >= 0 && p0 + 4 <= len) {
+                const v4f a = *(const v4f_u *)(xrow + p0);
+                v[4 * k] = a.x; v[4 * k + 1] = a.y; v[4 * k + 2] = a.z; v[4 * k + 3] = a.w;
+            } else {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) v[4 * k + c] = (g + 4 * k + c < total) ? xr[4 * k + c] : 0.0f;
+                for (int c = 0; c < 4; ++c) {
+                    const int e = q + 4 * k + c;
+                    const int p = e < lv ? pad_src(e, len, pad_left, pad_mode) : -1;
+                    v[4 * k + c] = p >= 0 ? xrow[p] : O::id();
+                }
+            }
+        }
+    } else {
+        const int64_t g = r * (int64_t)len + q;      // the strip's first input in x
+        const int64_t total = rows * (int64_t)len;
+        const float *xr = x + g;
+#pragma unroll
+        for (int k = 0; k < NL; ++k) {
+            if (g + 4 * k + 4 <= total) {
+                const v4f a = *(const v4f_u *)(xr + 4 * k);
+                v[4 * k] = a.x; v[4 * k + 1] = a.y; v[4 * k + 2] = a.z; v[4 * k + 3] = a.w;
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) v[4 * k + c] = (g + 4 * k + c < total) ? xr[4 * k + c] : 0.0f;
+            }
         }
     }
     float o[4];
@@ -78,8 +104,19 @@ __global__ __launch_bounds__(kWave) void slide_rows_kernel(const float *__restri
         o[3] = O::f(core, pre3);
     }
     if (OP == SWS_OP_ADD) {
+        if (PAD && pad_mode == SWS_PAD_SHRINK) {
+            // the window shrinks at the ends of the row: rescale by w / (real elements in it)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) o[c] *= scale;
+            for (int c = 0; c < 4; ++c) {
+                const int e = q + c;                 // first element of the window, in the extended row
+                const int hi = e + W < pad_left + len ? e + W : pad_left + len;
+                const int n = hi - (e > pad_left ? e : pad_left);
+                o[c] *= scale * (float)W / (float)(n > 0 ? n : 1);
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) o[c] *= scale;
+        }
     }
     float *yr = y + r * (int64_t)lo + q;
     if (q + 4 <= lo) {
@@ -93,7 +130,8 @@ __global__ __launch_bounds__(kWave) void slide_rows_kernel(const float *__restri
 }
 
 template <int OP, int W>
-hipError_t launch_rows_w(const float *x, float *y, int64_t rows, int len, int lo, float scale, hipStream_t s)
+hipError_t launch_rows_w(const float *x, float *y, int64_t rows, int len, int lo, float scale, bool padded,
+                         int pad_left, int pad_mode, hipStream_t s)
 {
     const int strips = (lo + 3) / 4;
     const int wg_per_row = (strips + kWave - 1) / kWave;
@@ -101,19 +139,24 @@ hipError_t launch_rows_w(const float *x, float *y, int64_t rows, int len, int lo
     const int recip = 65536 / strips + 1;
     const int64_t grid = rows_per_wg == 1 ? rows * wg_per_row : (rows + rows_per_wg - 1) / rows_per_wg;
     if (grid > 2147483647LL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((slide_rows_kernel<OP, W>), dim3((unsigned)grid), dim3(kWave), 0, s, x, y, rows, len, lo, scale,
-                       strips, wg_per_row, rows_per_wg, recip);
+    if (padded)
+        hipLaunchKernelGGL((slide_rows_kernel<OP, W, true>), dim3((unsigned)grid), dim3(kWave), 0, s, x, y, rows, len,
+                           lo, scale, strips, wg_per_row, rows_per_wg, recip, pad_left, pad_mode);
+    else
+        hipLaunchKernelGGL((slide_rows_kernel<OP, W, false>), dim3((unsigned)grid), dim3(kWave), 0, s, x, y, rows, len,
+                           lo, scale, strips, wg_per_row, rows_per_wg, recip, 0, 0);
     return hipGetLastError();
 }
 
 template <int OP, int W0>
-hipError_t launch_rows(const float *x, float *y, int64_t rows, int len, int lo, int w, float scale, hipStream_t s)
+hipError_t launch_rows(const float *x, float *y, int64_t rows, int len, int lo, int w, float scale, bool padded,
+                       int pad_left, int pad_mode, hipStream_t s)
 {
     if constexpr (W0 > kRowsMaxW) {
         return hipErrorInvalidValue;
     } else {
-        if (w == W0) return launch_rows_w<OP, W0>(x, y, rows, len, lo, scale, s);
-        return launch_rows<OP, W0 + 1>(x, y, rows, len, lo, w, scale, s);
+        if (w == W0) return launch_rows_w<OP, W0>(x, y, rows, len, lo, scale, padded, pad_left, pad_mode, s);
+        return launch_rows<OP, W0 + 1>(x, y, rows, len, lo, w, scale, padded, pad_left, pad_mode, s);
     }
 }
 
@@ -121,16 +164,17 @@ hipError_t launch_rows(const float *x, float *y, int64_t rows, int len, int lo, 
 
 int slide1d_rows_max_w() { return kRowsMaxW; }
 
-// Plain rows only.  hipErrorInvalidValue: w beyond the kernel's reach or a grid beyond the launch
-// limit (the caller then takes another kernel).
+// len: the physical row; lo: outputs per row (of the extended row when padded).
+// hipErrorInvalidValue: w beyond the kernel's reach or a grid beyond the launch limit (the caller
+// then takes another kernel).
 hipError_t launch_slide1d_rows(int op, const float *x, float *y, int64_t rows, int len, int lo, int32_t w, float scale,
-                               hipStream_t s)
+                               bool padded, int pad_left, int pad_mode, hipStream_t s)
 {
     if (w < 1 || w > kRowsMaxW) return hipErrorInvalidValue;
     switch (op) {
-    case SWS_OP_ADD: return launch_rows<SWS_OP_ADD, 1>(x, y, rows, len, lo, w, scale, s);
-    case SWS_OP_MAX: return launch_rows<SWS_OP_MAX, 1>(x, y, rows, len, lo, w, scale, s);
-    default: return launch_rows<SWS_OP_MIN, 1>(x, y, rows, len, lo, w, scale, s);
+    case SWS_OP_ADD: return launch_rows<SWS_OP_ADD, 1>(x, y, rows, len, lo, w, scale, padded, pad_left, pad_mode, s);
+    case SWS_OP_MAX: return launch_rows<SWS_OP_MAX, 1>(x, y, rows, len, lo, w, scale, padded, pad_left, pad_mode, s);
+    default: return launch_rows<SWS_OP_MIN, 1>(x, y, rows, len, lo, w, scale, padded, pad_left, pad_mode, s);
     }
 }
 

@@ -91,7 +91,7 @@ hipError_t launch_slide1d_pair(const float *u, const float *v, float *yu, float 
 // several rows per wavefront.  hipErrorInvalidValue: not taken (w or grid beyond its reach).
 int slide1d_rows_max_w();
 hipError_t launch_slide1d_rows(int op, const float *x, float *y, int64_t rows, int len, int lo, int32_t w, float scale,
-                               hipStream_t s);
+                               bool padded, int pad_left, int pad_mode, hipStream_t s);
 hipError_t launch_slide1d_generic(int op, const float *x, float *y, int64_t rows, int64_t len, int32_t w, float scale,
                                   hipStream_t s);
 hipError_t launch_pool2d(int op, const float *x, float *y, int64_t planes, int64_t H, int64_t W,

@@ -117,3 +117,29 @@ def test_shrinking_window_constant_row_and_argument_checks(B):
     assert np.abs(y - 3.0).max() < 1e-5
     with pytest.raises(B.SwsError):
         B.sws_slide1d_padded(0, to_gpu(x), 9, 9, 0, B.SWS_PAD_SHRINK, 1.0)
+
+
+@pytest.mark.parametrize("variant", [0, 7])
+@pytest.mark.parametrize("mode", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("w,pl,pr", [(1, 2, 1), (2, 1, 0), (3, 1, 1), (4, 0, 3), (5, 2, 2), (8, 7, 0), (9, 4, 4), (16, 8, 7),
+                                     (17, 0, 16), (25, 12, 12), (33, 16, 16), (33, 32, 0)])
+def test_padded_short_row_kernel(B, variant, mode, w, pl, pr):
+    """Rows of a few dozen to a few hundred elements with a boundary rule: the short-row kernel, as
+    the library chooses it and forced (option slide_variant 7, also on longer rows)."""
+    if mode == 4 and (pl >= w or pr >= w):
+        pytest.skip("a shrinking window keeps at least one real element")
+    B.sws_set_option("slide_variant", variant)
+    try:
+        for rows, length in ((7, 56), (300, 57), (40, 260), (130, 224), (5, 1031), (3, 5003), (64, 33), (9, 255)):
+            if mode == 1 and (pl > length - 1 or pr > length - 1):
+                continue
+            if mode == 2 and (pl > length or pr > length):
+                continue
+            r = _rng(mode * 131 + w * 7 + length)
+            x = (r.random((rows, length), dtype=np.float32) * 2 - 1).astype(np.float32)
+            for op in (0, 1, 2):
+                _check(B, op, x, w, pl, pr, mode, "short rows %dx%d w=%d pads=(%d,%d) mode=%d op=%d variant=%d" % (
+                    rows, length, w, pl, pr, mode, op, variant))
+    finally:
+        B.sws_set_option("slide_variant", 0)
+
