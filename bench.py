@@ -308,6 +308,19 @@ def sweeps_table(torch, B, workloads, iters=20):
                 del y
             del xd
         del xs
+    # planes of a few dozen elements, thousands of channels (a network's last stages)
+    for shape, geoms in (((32, 2048, 7, 7), ((7, 7, 1, 0), (3, 3, 1, 1))), ((32, 1024, 14, 14), ((3, 3, 2, 1), (2, 2, 2, 0)))):
+        xs = g(workloads.make(3, x_shape=shape)[0])
+        for k, _, st, pd in geoms:
+            ho = (shape[2] + 2 * pd - k) // st + 1
+            y = torch.empty(shape[0], shape[1], ho, ho, device="cuda")
+            for op, opn in ((1, "max"), (0, "avg")):
+                ms = time_launches(torch, lambda: B.sws_pool2d(op, xs, k, k, st, st, pd, pd, 1.0 / (k * k), y=y), iters)
+                nb = 4 * shape[0] * shape[1] * (shape[2] * shape[3] + ho * ho)
+                out["short_rows"]["f32_%spool%dx%d_s%d_%dx%dx%dx%d" % ((opn, k, k, st) + shape)] = {
+                    "us": round(ms * 1e3, 2), "GBps": round(nb / ms / 1e6, 1), "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+            del y
+        del xs
     torch.cuda.empty_cache()
     # the adjoints of the sliding dot product (training): configuration 5's depthwise layer (HBM-bound:
     # grad-input moves what the forward pass moves, grad-weight reads x and gy) and configuration 2's

@@ -526,12 +526,28 @@ hipError_t pool2d_16(int op, const T *x, T *y, int64_t planes, int H, int W, int
 
 }  // namespace
 
+constexpr int kSmallPlane = 256;                     // plane elements up to which the small-plane kernel is taken
+
 hipError_t launch_pool2d(int op, const float *x, float *y, int64_t planes, int64_t H, int64_t W, int64_t Ho,
                          int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
                          float scale, int div_valid, hipStream_t s)
 {
     // ph / pw are the top / left padding; the bottom / right padding is implied by Ho / Wo (cells
     // beyond the plane hold the identity whichever side they are on).
+    // option pool2d_variant 32 forces the small-plane kernel wherever it applies, 64 switches it off
+    // Its time goes with outputs x window cells, the band kernel's with planes.  Measured, max, us, small /
+    // band: 65536 planes of 7 x 7: 3 x 3 20 / 36, 7 x 7 -> 1 x 1 10 / 43, 2 x 2 s2 10 / 22; 10 x 10: 3 x 3
+    // 30 / 38; 32768 planes of 14 x 14: 3 x 3 s1 31 / 26, 3 x 3 s2 10 / 18, 2 x 2 s2 10 / 18; 16 x 16:
+    // 3 x 3 s1 35 / 19, 2 x 2 s2 10 / 12; 20 x 20: slower throughout.
+    const int64_t P = H * W, work = Ho * Wo * (int64_t)kh * kw;
+    const bool small = g_opt.pool2d_variant == 32 ||
+                       (g_opt.pool2d_variant != 64 && (P <= 100 || (P <= kSmallPlane && work <= 4 * P)));
+    if (g_opt.pool2d_variant != 1 && small) {
+        bool taken = false;
+        const hipError_t e = launch_pool2d_small(op, x, y, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw,
+                                                 scale, div_valid, s, &taken);
+        if (taken) return e;
+    }
     if (g_opt.pool2d_variant != 1) {
         bool taken = false;
         const hipError_t e = pool2d_tuned<float>(op, x, y, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph, pw,

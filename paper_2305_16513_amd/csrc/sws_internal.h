@@ -89,6 +89,11 @@ hipError_t launch_slide1d_pair(const float *u, const float *v, float *yu, float 
                                int32_t w, hipStream_t s);
 // Short rows, windows up to slide1d_rows_max_w(): four outputs per lane from shifted 128-bit loads,
 // several rows per wavefront.  hipErrorInvalidValue: not taken (w or grid beyond its reach).
+// 2-D pooling on planes of a few hundred elements: several whole planes per workgroup through LDS.
+// *taken = false: not its case (the caller goes on to the other kernels).
+hipError_t launch_pool2d_small(int op, const float *x, float *y, int64_t planes, int H, int W, int Ho, int Wo, int kh,
+                               int kw, int sh, int sw, int ph, int pw, float scale, int div_valid, hipStream_t s,
+                               bool *taken);
 int slide1d_rows_max_w();
 hipError_t launch_slide1d_rows(int op, const float *x, float *y, int64_t rows, int len, int lo, int32_t w, float scale,
                                bool padded, int pad_left, int pad_mode, hipStream_t s);

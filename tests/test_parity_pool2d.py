@@ -200,3 +200,59 @@ def test_more_than_2_to_the_32_elements(B):
     assert_within_tol(to_host(gx.view(planes, 112, 112)[sample]).reshape(ref.shape), ref, mag, "big average pool adjoint")
     del x, gy, gx
     torch.cuda.empty_cache()
+
+
+SMALL_GEOMS = [(3, 3, 1, 1, 1, 1), (3, 3, 2, 2, 1, 1), (2, 2, 2, 2, 0, 0), (7, 7, 1, 1, 0, 0), (7, 7, 1, 1, 3, 3), (5, 3, 1, 2, 2, 0),
+               (1, 1, 1, 1, 0, 0), (4, 4, 4, 4, 0, 0), (2, 5, 1, 3, 1, 4)]
+
+
+@pytest.mark.parametrize("variant", [0, 32, 64])
+@pytest.mark.parametrize("geom", SMALL_GEOMS)
+@pytest.mark.parametrize("shape", [(3, 700, 7, 7), (2, 333, 14, 14), (5, 41, 5, 9), (1, 67, 16, 16), (2, 9, 1, 1), (1, 13, 3, 300),
+                                   (1, 5, 32, 32), (1, 3, 33, 31)])
+def test_small_planes(B, variant, geom, shape):
+    """Planes of a few hundred elements, thousands of them: the small-plane kernel (several planes
+    per workgroup), as the library chooses it, forced (option pool2d_variant 32, planes up to 1024
+    elements) and switched off (64); a last workgroup with fewer planes; x off the 16-byte boundary."""
+    import torch
+    kh, kw, sh, sw, ph, pw = geom
+    n, c, h, w = shape
+    if h + 2 * ph < kh or w + 2 * pw < kw or ph >= kh or pw >= kw:
+        pytest.skip("window does not fit")
+    r = np.random.Generator(np.random.PCG64(kh * 100 + kw * 10 + h * 7 + w))
+    x = r.standard_normal(shape, dtype=np.float32)
+    B.sws_set_option("pool2d_variant", variant)
+    try:
+        for shift in (0, 1):
+            xbuf = torch.zeros(x.size + 4, device="cuda")
+            xs = xbuf[shift:shift + x.size].view(shape)
+            xs.copy_(torch.from_numpy(x))
+            for op in ("add", "max", "min"):
+                scale = 1.0 / (kh * kw)
+                y = to_host(B.sws_pool2d(OPS[op], xs, kh, kw, sh, sw, ph, pw, scale))
+                ref, mag = oracle.pool2d(OPS[op], x, kh, kw, sh, sw, ph, pw, scale)
+                what = "small planes %s %s %s variant %d shift %d" % (shape, geom, op, variant, shift)
+                if op == "add":
+                    assert_within_tol(y, ref, mag, what)
+                else:
+                    assert_bit_exact(y, ref, what)
+    finally:
+        B.sws_set_option("pool2d_variant", 0)
+
+
+@pytest.mark.parametrize("divisor", [0, 1])
+@pytest.mark.parametrize("geom", EX_GEOMS)
+@pytest.mark.parametrize("shape", [(3, 500, 7, 7), (2, 99, 14, 14), (1, 30, 9, 20)])
+def test_small_planes_four_sided_padding_and_real_cell_average(B, divisor, geom, shape):
+    kh, kw, sh, sw, pads = geom
+    r = np.random.Generator(np.random.PCG64(kh * 100 + kw * 10 + sh + sum(pads) + shape[2]))
+    x = r.standard_normal(shape, dtype=np.float32)
+    scale = 1.0 if divisor else 1.0 / (kh * kw)
+    for op in ((0,) if divisor else (0, 1, 2)):
+        y = to_host(B.sws_pool2d_ex(op, to_gpu(x), kh, kw, sh, sw, pads, divisor, scale))
+        ref, mag = oracle.pool2d_ex(op, x, kh, kw, sh, sw, pads, bool(divisor), scale)
+        if op == 0:
+            assert_within_tol(y, ref, mag, "small pool2d_ex %s %s div=%d" % (shape, geom, divisor))
+        else:
+            assert_bit_exact(y, ref, "small pool2d_ex %s %s op=%d" % (shape, geom, op))
+
