@@ -327,15 +327,14 @@ def test_cfg2_conv1d_full_size(B):
 
 
 def test_cfg4_conv2d_full_size(B):
-    """[32, 64, 56, 56] x [64, 64, 3, 3], pad 1: full launch; the oracle checks the first,
-    the last and three seeded images completely (each 200,704 outputs of 576 terms)."""
+    """[32, 64, 56, 56] x [64, 64, 3, 3], pad 1: one launch, all 32 images against the oracle,
+    every one of the 6,422,528 outputs (576 terms each)."""
     x, w = workloads.make(4)
     workloads.check_clean(x)
     y = to_host(B.sws_conv2d(to_gpu(x), to_gpu(w), 1, 1, 1, 1))
-    imgs = sorted(set([0, 31] + _rng(44).integers(0, 32, size=3).tolist()))
-    ref, mag = oracle.conv2d(x[imgs], w, 1, 1, 1, 1)
-    assert_within_tol(y[imgs], ref, mag, "cfg4 conv2d")
-    assert np.isfinite(y).all()
+    ref, mag = oracle.conv2d(x, w, 1, 1, 1, 1)
+    worst = assert_within_tol(y, ref, mag, "cfg4 conv2d")
+    assert worst < 2e-6
 
 
 def test_conv2d_more_than_2_to_the_32_elements(B):

@@ -106,24 +106,19 @@ def test_tiny_planes(B):
 
 
 @pytest.mark.parametrize("stride", [1, 2])
-def test_cfg3_full_size_sampled_planes(B, stride):
-    """[32, 64, 112, 112], 3x3, pad 1, stride 1 and 2, at full size in one launch; the
-    oracle checks a seeded sample of whole planes plus the first and last plane, and a
-    size-independent property covers every output: max >= centre tap, and the stride-2
-    result is the stride-1 result subsampled."""
+def test_cfg3_full_size_every_plane(B, stride):
+    """[32, 64, 112, 112], 3x3, pad 1, stride 1 and 2, at full size in one launch: all 2048
+    planes against the oracle, every output; and the stride-2 result is the stride-1 result
+    subsampled."""
     import torch
     x, _ = workloads.make(3)
     xg = to_gpu(x)
-    rng = np.random.Generator(np.random.PCG64(33 + stride))
-    planes = sorted(set([0, 2047] + rng.integers(0, 2048, size=30).tolist()))
-    xs = x.reshape(2048, 1, 112, 112)[planes]
     for op in ("max", "add"):
         yg = B.sws_pool2d(OPS[op], xg, 3, 3, stride, stride, 1, 1, 1.0 / 9)
-        y = to_host(yg).reshape(2048, 1, yg.shape[2], yg.shape[3])[planes]
-        ref, mag = oracle.pool2d(OPS[op], xs, 3, 3, stride, stride, 1, 1, 1.0 / 9)
+        y = to_host(yg)
+        ref, mag = oracle.pool2d(OPS[op], x, 3, 3, stride, stride, 1, 1, 1.0 / 9)
         if op == "max":
             assert_bit_exact(y, ref, "cfg3 max s%d" % stride)
-            assert bool((yg >= xg[:, :, ::stride, ::stride]).all())
         else:
             assert_within_tol(y, ref, mag, "cfg3 avg s%d" % stride)
         if stride == 2:
