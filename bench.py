@@ -38,6 +38,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ops", action="store_true", help="skip the per-operator table of configs 1-4")
+    ap.add_argument("--cold", action="store_true",
+                    help="with --only cfg2_* / cfg3_* / cfg4_*: go round enough distinct buffer pairs that more than "
+                         "512 MB is touched between reuses (the tensors of those configurations fit the last-level cache)")
     ap.add_argument("--only", default=None,
                     help="profiling aid: launch just this operator --steps times and print nothing but a "
                          "short note (names: the keys of 'kernels' and 'ops', or 'copy' for the 2 GiB "
@@ -63,21 +66,23 @@ def read_traffic(name):
 
 
 def time_launches(torch, fn, iters, warm=8):
-    """Mean duration in ms of `fn` (one launch) from events on the current stream."""
+    """Mean duration in ms of `fn` (one launch): `iters` back-to-back launches between two events on
+    the current stream.  An event recorded after every launch keeps the next kernel from starting
+    until the event has been written (measured: 3.7 us per launch on a 35 us kernel), so only the
+    two ends are marked."""
     for _ in range(warm):
         fn()
     torch.cuda.synchronize()
-    evs = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
-    evs[0].record()
-    for i in range(iters):
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
         fn()
-        evs[i + 1].record()
+    e1.record()
     torch.cuda.synchronize()
-    ts = [evs[i].elapsed_time(evs[i + 1]) for i in range(iters)]
-    return sum(ts) / len(ts)
+    return e0.elapsed_time(e1) / iters
 
 
-def ops_table(torch, B, workloads, iters=20):
+def ops_table(torch, B, workloads, iters=40):
     """Each operator of configurations 1-4 on its own.  These tensors fit in the 256 MB
     last-level cache, so besides the warm figure a cold one is taken by rotating through
     enough distinct buffers that more than 512 MB is touched between reuses."""
@@ -408,9 +413,23 @@ def sweeps_table(torch, B, workloads, iters=20):
     return out
 
 
-def run_only(torch, B, workloads, name, steps):
+def run_only(torch, B, workloads, name, steps, cold=False):
     """Launch one operator `steps` times (for rocprofv3 runs that should see a single kernel)."""
     g = lambda a: torch.from_numpy(a).cuda()
+
+    def rotating(x, y):
+        """fn(launch) -> a call that goes round copies of (x, y): more than 600 MB between reuses if cold."""
+        nbytes = x.numel() * x.element_size() + y.numel() * y.element_size()
+        n = int(600e6 // nbytes) + 1 if cold else 1
+        sets = [(x, y)] + [(x.clone(), torch.empty_like(y)) for _ in range(n - 1)]
+        state = {"i": 0}
+
+        def wrap(launch):
+            def call():
+                state["i"] = (state["i"] + 1) % n
+                launch(*sets[state["i"]])
+            return call
+        return wrap
     if name == "copy":
         src = torch.rand(ROWS5, LEN5, device="cuda")
         dst = torch.empty_like(src)
@@ -486,7 +505,7 @@ def run_only(torch, B, workloads, name, steps):
         x2 = g(workloads.make(2)[0])
         y = torch.empty(16, 64, 4094, device="cuda")
         op = 1 if "max" in name else 0
-        fn = lambda: B.sws_slide1d(op, x2, 3, 1 / 3, y=y)
+        fn = rotating(x2, y)(lambda xx, yy: B.sws_slide1d(op, xx, 3, 1 / 3, y=yy))
     elif name.startswith("layer_"):                       # layer_<s2_3x3_128ch_56x56|s1_3x3_256ch_14x14>_<forward|grad_input|grad_weight>
         tag, what = (name[6:].rsplit("_", 2)[0], "_".join(name.rsplit("_", 2)[1:])) if name.endswith(("grad_input", "grad_weight")) else (name[6:].rsplit("_", 1)[0], "forward")
         ch, hh, st = {"s2_3x3_128ch_56x56": (128, 56, 2), "s1_3x3_256ch_14x14": (256, 14, 1)}[tag]
@@ -518,17 +537,17 @@ def run_only(torch, B, workloads, name, steps):
         ho = 112 if s == 1 else 56
         y = torch.empty(32, 64, ho, ho, device="cuda")
         op = 1 if "max" in name else 0
-        fn = lambda: B.sws_pool2d(op, x3, 3, 3, s, s, 1, 1, 1 / 9, y=y)
+        fn = rotating(x3, y)(lambda xx, yy: B.sws_pool2d(op, xx, 3, 3, s, s, 1, 1, 1 / 9, y=yy))
     elif name == "cfg4_conv2d_3x3":
         x4, w4 = workloads.make(4)
         x4, w4 = g(x4), g(w4)
         y = torch.empty(32, 64, 56, 56, device="cuda")
-        fn = lambda: B.sws_conv2d(x4, w4, 1, 1, 1, 1, y=y)
+        fn = rotating(x4, y)(lambda xx, yy: B.sws_conv2d(xx, w4, 1, 1, 1, 1, y=yy))
     elif name == "cfg2_conv1d_64x64x3":
         x2, w2 = workloads.make(2)
         x2, w2 = g(x2), g(w2)
         y = torch.empty(16, 64, 4094, device="cuda")
-        fn = lambda: B.sws_conv1d(x2, w2, y=y)
+        fn = rotating(x2, y)(lambda xx, yy: B.sws_conv1d(xx, w2, y=yy))
     elif name == "exp_dwconv_k51_d8":
         x7, taps = workloads.make(7)
         x7, taps = g(x7), g(taps)
@@ -553,7 +572,7 @@ def run_only(torch, B, workloads, name, steps):
     for _ in range(steps):
         fn()
     torch.cuda.synchronize()
-    print(json.dumps({"only": name, "launches": steps}))
+    print(json.dumps({"only": name, "launches": steps, "cold": bool(cold)}))
 
 
 def cpu_baseline(x_host, taps_host):
@@ -610,7 +629,7 @@ def main():
         sys.exit(2)
     B.lib()                                       # fail loudly if the HIP library is missing
     if args.only:
-        run_only(torch, B, workloads, args.only, args.steps)
+        run_only(torch, B, workloads, args.only, args.steps, args.cold)
         return
 
     x_host, taps_host = workloads.make(5)

@@ -40,6 +40,8 @@ template <> struct Io<float> {
         if (plain) *(v4f_u *)p = o;
         else __builtin_nontemporal_store(o, (v4f_u *)p);
     }
+    typedef v2f v2f_u __attribute__((aligned(4)));
+    static __device__ __forceinline__ void store2_nt(float *p, v2f o) { __builtin_nontemporal_store(o.x, p); __builtin_nontemporal_store(o.y, p + 1); }
 };
 template <typename T> struct Io16 {
     typedef T v4 __attribute__((ext_vector_type(4)));
@@ -54,6 +56,9 @@ template <typename T> struct Io16 {
         if (plain) *(v4_u *)p = h;
         else __builtin_nontemporal_store(h, (v4_u *)p);
     }
+    typedef T v2 __attribute__((ext_vector_type(2)));
+    typedef v2 v2_u __attribute__((aligned(2)));
+    static __device__ __forceinline__ void store2_nt(T *p, v2f o) { __builtin_nontemporal_store(__builtin_convertvector(o, v2), (v2_u *)p); }
 };
 template <> struct Io<__bf16> : Io16<__bf16> {};
 template <> struct Io<_Float16> : Io16<_Float16> {};
@@ -78,16 +83,29 @@ __global__ __launch_bounds__(kThreads) void pool2d_band_kernel(
     constexpr int NG = (OFF + NC + 3) / 4;           // aligned 4-column groups per input row
     extern __shared__ __attribute__((aligned(16))) float lds_all[];
 
-    // flag bits: 2 = XCD-contiguous placement of workgroups (default: launch order), 4 = plain stores,
+    // flag bits: 2 = XCD-contiguous placement of workgroups (default: launch order),
     // 8 = ADD results are divided by the number of window cells inside the plane
-    const int64_t wg = (flags & 2) ? xcd_unit((n_units + kWaves - 1) / kWaves) : (int64_t)blockIdx.x;
-    if (wg < 0) return;
+    const int wpb = blockDim.x >> 6;                 // wavefronts per workgroup
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t unit = wg * kWaves + wave;          // one band per wavefront
-    if (unit >= n_units) return;
+    int64_t plane;
+    int band;
+    if (flags & 16) {
+        // workgroup b runs on XCD b mod 8: XCD x takes the planes 8q + x, band by band, so that the
+        // eight L2s work on eight adjacent planes and a band's halo rows are in the L2 that fetched them
+        const int64_t k = ((int64_t)blockIdx.x >> 3) * wpb + wave;
+        const int64_t q = k / bands;
+        band = (int)(k - q * bands);
+        plane = q * kXcd + (blockIdx.x & 7);
+        if (plane * bands + band >= n_units) return;
+    } else {
+        const int64_t wg = (flags & 2) ? xcd_unit((n_units + wpb - 1) / wpb) : (int64_t)blockIdx.x;
+        if (wg < 0) return;
+        const int64_t unit = wg * wpb + wave;         // one band per wavefront
+        if (unit >= n_units) return;
+        plane = unit / bands;
+        band = (int)(unit - plane * bands);
+    }
     float *lds = lds_all + wave * lds_floats;
-    const int64_t plane = unit / bands;
-    const int band = (int)(unit - plane * bands);
     const T *xp = x + plane * (int64_t)H * W;
     T *yp = y + plane * (int64_t)Ho * Wo;
     const int ho0 = band * TH;                       // first output row of the band
@@ -105,17 +123,35 @@ __global__ __launch_bounds__(kThreads) void pool2d_band_kernel(
         const T *src = xp + (int64_t)row_lo * W;
         const int n = (row_hi - row_lo) * W;         // multiple of 4, at most kLdsBudget / 4
         constexpr int NL = kLdsBudget / 16 / kWave;
+        // Loads go in four chunks, the third and fourth only if the band reaches them (wave-uniform
+        // tests), so that a short band does not issue loads it drops.  (Streaming loads for the rows no
+        // other band stages were measured: no difference.)
+        constexpr int NQ = NL / 4;
         v4f g[NL];
+        auto load = [&](int j0, int j1) {
 #pragma unroll
-        for (int j = 0; j < NL; ++j) {
-            const int i = 4 * (lane + kWave * j);
-            g[j] = IO::load4(src + (i < n ? i : 0));
-        }
+            for (int j = j0; j < j1; ++j) {
+                const int i = 4 * (lane + kWave * j);
+                g[j] = IO::load4(src + (i < n ? i : 0));
+            }
+        };
+        auto keep = [&](int j0, int j1) {
 #pragma unroll
-        for (int j = 0; j < NL; ++j) {
-            const int i = 4 * (lane + kWave * j);
-            if (i < n) *(v4f *)(lds + i) = g[j];
+            for (int j = j0; j < j1; ++j) {
+                const int i = 4 * (lane + kWave * j);
+                if (i < n) *(v4f *)(lds + i) = g[j];
+            }
+        };
+        load(0, 2 * NQ);
+        if (n > 4 * kWave * 2 * NQ) {
+            load(2 * NQ, 3 * NQ);
+            if (n > 4 * kWave * 3 * NQ) {
+                load(3 * NQ, NL);
+                keep(3 * NQ, NL);
+            }
+            keep(2 * NQ, 3 * NQ);
         }
+        keep(0, 2 * NQ);
     } else {
         const int n = (row_hi - row_lo) * P;
         for (int i = lane; i < n; i += kWave) {
@@ -179,12 +215,9 @@ __global__ __launch_bounds__(kThreads) void pool2d_band_kernel(
             }
             T *dst = yp + (int64_t)(ho + ro) * Wo + 4 * cg;
             if (4 * cg + 4 <= Wo) {
-                if constexpr (sizeof(T) == 4) {
-                    if (flags & 4) *(v4f_u *)dst = (v4f){o[0], o[1], o[2], o[3]};
-                    else __builtin_nontemporal_store((v4f){o[0], o[1], o[2], o[3]}, (v4f_u *)dst);
-                } else {
-                    IO::store4(dst, (v4f){o[0], o[1], o[2], o[3]}, (flags & 4) != 0);
-                }
+                // always non-temporal: a run-time choice between a plain and a non-temporal store of the
+                // same value makes the compiler merge the two into one plain store
+                IO::store4(dst, (v4f){o[0], o[1], o[2], o[3]}, false);
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
@@ -228,12 +261,18 @@ hipError_t launch_band(const T *x, T *y, int64_t planes, int H, int W, int Ho, i
     *taken = p.ok;
     if (!p.ok) return hipSuccess;
     const int64_t n_units = planes * p.bands;
-    const int flags = (g_opt.pool2d_variant & 6) | (div_valid ? 8 : 0);
-    const int64_t n_wg = (n_units + kWaves - 1) / kWaves;
-    const int64_t grid = (flags & 2) ? xcd_grid(n_wg) : n_wg;
+    // default: single-wavefront workgroups, planes dealt cyclically to the XCDs (measured on [2048,112,112]
+    // under rotating buffers: 36.0 / 22.7 us at stride 1 / 2 against 37.0 / 23.2 us for four-wavefront
+    // workgroups in launch order, which option bit 512 brings back; bit 2: the XCD-contiguous placement)
+    const bool old_shape = (g_opt.pool2d_variant & (512 | 2)) != 0;
+    const int flags = (g_opt.pool2d_variant & 2) | (old_shape ? 0 : 16) | (div_valid ? 8 : 0);
+    const int wpb = old_shape ? kWaves : 1;
+    const int64_t n_wg = (n_units + wpb - 1) / wpb;
+    int64_t grid = (flags & 2) ? xcd_grid(n_wg) : n_wg;
+    if (flags & 16) grid = (((planes + kXcd - 1) / kXcd * p.bands + wpb - 1) / wpb) * kXcd;
     if (grid > 2147483647LL) { *taken = false; return hipSuccess; }
-    hipLaunchKernelGGL((pool2d_band_kernel<OP, KH, KW, SH, SW, PW, T>), dim3((unsigned)grid), dim3(kThreads),
-                       p.lds_bytes * kWaves, s, x, y, H, W, Ho, Wo, ph, p.P, p.TH, p.bands, scale, n_units,
+    hipLaunchKernelGGL((pool2d_band_kernel<OP, KH, KW, SH, SW, PW, T>), dim3((unsigned)grid), dim3(wpb * kWave),
+                       p.lds_bytes * wpb, s, x, y, H, W, Ho, Wo, ph, p.P, p.TH, p.bands, scale, n_units,
                        (int)(p.lds_bytes / 4), flags);
     return hipGetLastError();
 }
@@ -430,6 +469,138 @@ hipError_t launch_sep(const T *x, T *y, int64_t planes, int H, int W, int Ho, in
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------
+// Row-streaming kernel for the small windows of pooling layers on planes whose rows fit a wavefront
+// (W a multiple of 4, W <= 256), without LDS.  A lane owns four adjacent columns; the W/4 lanes of a
+// group load one input row as one contiguous run of 128-bit accesses, and the G = 64 / (W/4) groups of
+// a wavefront take G consecutive bands of TH output rows.  A lane keeps the (TH-1)*S + K rows of its
+// band in registers, forms the sliding sum down H on them, and gets the few columns its windows need
+// from the neighbouring lanes by DPP lane shifts (the Slide of Section 3 between registers) for the
+// sliding sum along W.  A wavefront is short-lived (a few loads, a few stores) and is a workgroup of
+// its own: the shape in which this GPU's memory system streams fastest.  Workgroup b runs on XCD
+// b mod 8; XCD x takes the planes 8q + x band by band, so the rows two bands share are in the L2 that
+// fetched them and the eight L2s sweep eight adjacent planes.
+// Stride 1 needs Wo = W (window centred: 2 PW = K - 1), stride 2 needs Wo = W / 2.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float lane_before(float v)       // the value held by lane - 1 (0 for lane 0)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x138, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float lane_after(float v)        // the value held by lane + 1 (0 for lane 63)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x130, 0xf, 0xf, false));
+}
+
+template <int OP, int K, int S, int PW, int TH, typename T>
+__global__ __launch_bounds__(kWave) void pool2d_rows_kernel(const T *__restrict__ x, T *__restrict__ y, int H, int W,
+                                                            int Ho, int Wo, int ph, int LPR, int G, int lpr_rcp,
+                                                            int64_t planes, float scale)
+{
+    using O = Op<OP>;
+    using IO = Io<T>;
+    constexpr int NL = PW;                                           // columns wanted from the lane before
+    constexpr int NRT = (S == 1) ? K - 1 - PW : (K - 2 - PW > 0 ? K - 2 - PW : 0);   // ... from the lane after
+    constexpr int NOUT = (S == 1) ? 4 : 2;                           // outputs per lane and row
+    constexpr int NR = (TH - 1) * S + K;                             // input rows of a band
+    static_assert(NL <= 4 && NRT <= 4, "windows reach the immediate neighbour lanes only");
+    const int lane = threadIdx.x;
+    const int grp = (lane * lpr_rcp) >> 16, l = lane - grp * LPR;    // lane / LPR (exact for lane < 64)
+    if (grp >= G) return;
+    // grid: x = 8 * (wavefront of the plane) + XCD, y = round of eight planes.  Workgroups are dealt to
+    // the XCDs by their linear index, and gridDim.x is a multiple of 8.
+    const int sl = (int)(blockIdx.x >> 3);
+    const int64_t plane = (int64_t)blockIdx.y * kXcd + (blockIdx.x & 7);
+    if (plane >= planes) return;
+    const int ho0 = (sl * G + grp) * TH;                             // first output row of my band
+    if (ho0 >= Ho) return;
+    const T *xp = x + plane * (int64_t)H * W + 4 * l;
+    T *yp = y + plane * (int64_t)Ho * Wo + NOUT * l;
+    const v4f id4 = {O::id(), O::id(), O::id(), O::id()};
+    v4f r[NR];
+#pragma unroll
+    for (int j = 0; j < NR; ++j) {                                   // all loads in flight together
+        const int row = ho0 * S - ph + j;
+        const bool ok = row >= 0 && row < H;
+        const v4f v = IO::load4(xp + (int64_t)(ok ? row : 0) * W);
+        r[j] = ok ? v : id4;                                         // rows outside the plane hold the identity
+    }
+    const bool first = l == 0, last = l == LPR - 1;
+#pragma unroll
+    for (int i = 0; i < TH; ++i) {
+        // sliding sum down H on the lane's four columns ...
+        float e[NL + 4 + NRT];
+        v4f v = r[i * S];
+#pragma unroll
+        for (int a = 1; a < K; ++a) {
+            v.x = O::f(v.x, r[i * S + a].x); v.y = O::f(v.y, r[i * S + a].y);
+            v.z = O::f(v.z, r[i * S + a].z); v.w = O::f(v.w, r[i * S + a].w);
+        }
+        e[NL] = v.x; e[NL + 1] = v.y; e[NL + 2] = v.z; e[NL + 3] = v.w;
+        // ... the columns beside them from the neighbouring lanes (identity beyond the plane's edges) ...
+#pragma unroll
+        for (int t = 0; t < NL; ++t) {
+            const float nb = lane_before(e[NL + 3 - t]);
+            e[NL - 1 - t] = first ? O::id() : nb;
+        }
+#pragma unroll
+        for (int t = 0; t < NRT; ++t) {
+            const float nb = lane_after(e[NL + t]);
+            e[NL + 4 + t] = last ? O::id() : nb;
+        }
+        // ... then along W, operands in column order
+        float o[NOUT];
+#pragma unroll
+        for (int c = 0; c < NOUT; ++c) {
+            float acc = e[c * S];
+#pragma unroll
+            for (int b = 1; b < K; ++b) acc = O::f(acc, e[c * S + b]);
+            o[c] = (OP == SWS_OP_ADD) ? acc * scale : acc;
+        }
+        const int ho = ho0 + i;
+        if (ho < Ho) {
+            if constexpr (NOUT == 4) IO::store4(yp + (int64_t)ho * Wo, (v4f){o[0], o[1], o[2], o[3]}, false);
+            else IO::store2_nt(yp + (int64_t)ho * Wo, (v2f){o[0], o[1]});
+        }
+    }
+}
+
+template <int OP, int K, int S, int PW, int TH, typename T>
+hipError_t launch_rows(const T *x, T *y, int64_t planes, int H, int W, int Ho, int Wo, int ph, float scale,
+                       hipStream_t s, bool *taken)
+{
+    const int LPR = W / 4, G = kWave / LPR;
+    const int bands = (Ho + TH - 1) / TH;
+    const int spp = (bands + G - 1) / G;                             // wavefronts per plane
+    const int64_t rounds = (planes + kXcd - 1) / kXcd;
+    *taken = rounds <= 65535;
+    if (!*taken) return hipSuccess;
+    hipLaunchKernelGGL((pool2d_rows_kernel<OP, K, S, PW, TH, T>), dim3((unsigned)(spp * kXcd), (unsigned)rounds), dim3(kWave),
+                       0, s, x, y, H, W, Ho, Wo, ph, LPR, G, (65536 + LPR - 1) / LPR, planes, scale);
+    return hipGetLastError();
+}
+
+// The geometries the row-streaming kernel is built for: 3 x 3 with one column of padding at stride 1
+// and 2, 2 x 2 stride 2 without padding; rows of 4 .. 256 elements in multiples of 4; every output
+// divided by the same number.  Band heights as measured on [2048, 112, 112] under rotating buffers:
+// two output rows per lane at stride 1 (35.0 us against 36.5 with one and 35.2 with four), one at stride 2
+// (21.8 us against 23.9 with two).
+template <int OP, typename T>
+hipError_t dispatch_rows(const T *x, T *y, int64_t planes, int H, int W, int Ho, int Wo, int kh, int kw, int sh,
+                         int sw, int ph, int pw, float scale, int div_valid, hipStream_t s, bool *taken)
+{
+    *taken = false;
+    if (div_valid || kh != kw || sh != sw || (W & 3) || W < 4 || W > 256 || ph < 0 || ph >= kh ||
+        (g_opt.pool2d_variant & 128))
+        return hipSuccess;
+    if (kh == 3 && sh == 1 && pw == 1 && Wo == W)
+        return launch_rows<OP, 3, 1, 1, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+    if (kh == 3 && sh == 2 && pw == 1 && Wo == W / 2)
+        return launch_rows<OP, 3, 2, 1, 1, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+    if (kh == 2 && sh == 2 && pw == 0 && Wo == W / 2)
+        return launch_rows<OP, 2, 2, 0, 1, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+    return hipSuccess;
+}
+
 template <int OP, typename T>
 hipError_t dispatch_band(const T *x, T *y, int64_t planes, int H, int W, int Ho, int Wo, int kh, int kw,
                          int sh, int sw, int ph, int pw, float scale, int div_valid, hipStream_t s, bool *taken)
@@ -460,6 +631,12 @@ hipError_t pool2d_tuned(int op, const T *x, T *y, int64_t planes, int H, int W, 
                         int sw, int ph, int pw, float scale, int div_valid, hipStream_t s, bool *taken)
 {
     hipError_t e;
+    switch (op) {
+    case SWS_OP_ADD: e = dispatch_rows<SWS_OP_ADD, T>(x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, div_valid, s, taken); break;
+    case SWS_OP_MAX: e = dispatch_rows<SWS_OP_MAX, T>(x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, div_valid, s, taken); break;
+    default: e = dispatch_rows<SWS_OP_MIN, T>(x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, div_valid, s, taken); break;
+    }
+    if (*taken) return e;
     switch (op) {
     case SWS_OP_ADD: e = dispatch_band<SWS_OP_ADD, T>(x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, div_valid, s, taken); break;
     case SWS_OP_MAX: e = dispatch_band<SWS_OP_MAX, T>(x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, div_valid, s, taken); break;

@@ -64,9 +64,10 @@ def test_add_bit_exact_on_integer_valued_input(B):
     assert np.array_equal(y.astype(np.float64), ref)
 
 
-@pytest.mark.parametrize("flags", [2, 4, 6])
+@pytest.mark.parametrize("flags", [128, 128 | 2, 128 | 512])
 def test_band_kernel_knobs(B, flags):
-    """XCD-contiguous placement and plain stores are measurement knobs, not semantics."""
+    """The band kernel where the row-streaming kernel would be taken (128), with the XCD-contiguous
+    placement (2) or four-wavefront workgroups in launch order (512): measurement knobs, not semantics."""
     x = np.random.Generator(np.random.PCG64(flags)).standard_normal((3, 5, 60, 112), dtype=np.float32)
     B.sws_set_option("pool2d_variant", flags)
     try:
@@ -74,6 +75,60 @@ def test_band_kernel_knobs(B, flags):
         _check(B, "add", x, 3, 3, 2, 2, 1, 1)
     finally:
         B.sws_set_option("pool2d_variant", 0)
+
+
+ROW_SHAPES = [(1, 1, 1, 4), (2, 3, 5, 8), (3, 2, 9, 28), (2, 9, 56, 56), (1, 11, 112, 112), (2, 2, 31, 224), (1, 3, 7, 256),
+              (1, 17, 3, 36), (19, 1, 2, 100)]
+
+
+@pytest.mark.parametrize("band_kernel", [False, True])
+@pytest.mark.parametrize("op", ["add", "max", "min"])
+@pytest.mark.parametrize("geom", [(3, 1, 1), (3, 2, 1), (2, 2, 0)])
+@pytest.mark.parametrize("shape", ROW_SHAPES)
+def test_row_streaming_kernel(B, band_kernel, op, geom, shape):
+    """3 x 3 pad 1 at stride 1 and 2 and 2 x 2 stride 2 on rows of 4 .. 256 elements (multiples of 4) run on the
+    kernel without LDS: one to sixteen lane groups per wavefront, planes that end inside the last round of
+    eight, odd heights, x off the 16-byte boundary.  Option pool2d_variant 128 puts the same calls on the band
+    kernel; both must agree with the oracle."""
+    import torch
+    k, s, p = geom
+    n, c, h, w = shape
+    if s == 2 and w % 2:
+        pytest.skip("odd width")
+    rng = np.random.Generator(np.random.PCG64(1000 * k + 100 * s + h * w + n))
+    x = rng.standard_normal(shape, dtype=np.float32)
+    flat = torch.empty(x.size + 1, device="cuda")
+    xg = flat[1:].view(shape)                         # 4-byte aligned only
+    xg.copy_(to_gpu(x))
+    scale = 1.0 / (k * k)
+    B.sws_set_option("pool2d_variant", 128 if band_kernel else 0)
+    try:
+        for ph in sorted({p, 0, k - 1}):
+            if h + 2 * ph < k:
+                continue
+            y = to_host(B.sws_pool2d(OPS[op], xg, k, k, s, s, ph, p, scale))
+            ref, mag = oracle.pool2d(OPS[op], x, k, k, s, s, ph, p, scale)
+            what = "rows kernel %s %s ph=%d %s" % (op, geom, ph, shape)
+            if op == "add":
+                assert_within_tol(y, ref, mag, what)
+            else:
+                assert_bit_exact(y, ref, what)
+    finally:
+        B.sws_set_option("pool2d_variant", 0)
+
+
+def test_row_streaming_kernel_guard_band(B):
+    """Nothing is written outside y: guard elements around the output keep their value."""
+    import torch
+    x = np.random.Generator(np.random.PCG64(77)).standard_normal((5, 3, 21, 44), dtype=np.float32)
+    for k, s, p in ((3, 1, 1), (3, 2, 1), (2, 2, 0)):
+        ho, wo = (21 + 2 * p - k) // s + 1, (44 + 2 * p - k) // s + 1
+        buf = torch.full((15 * ho * wo + 64,), 12345.0, device="cuda")
+        y = buf[32:32 + 15 * ho * wo].view(5, 3, ho, wo)
+        B.sws_pool2d(1, to_gpu(x), k, k, s, s, p, p, 1.0, y=y)
+        ref, _ = oracle.pool2d(1, x, k, k, s, s, p, p, 1.0)
+        assert_bit_exact(to_host(y), ref, "guarded %s" % ((k, s, p),))
+        assert bool((buf[:32] == 12345.0).all()) and bool((buf[32 + 15 * ho * wo:] == 12345.0).all())
 
 
 @pytest.mark.parametrize("op", ["add", "max"])
