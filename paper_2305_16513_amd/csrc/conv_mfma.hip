@@ -672,6 +672,12 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
         W *= H; H = 1;
         Wo *= Ho; Ho = 1;
     }
+    // the weight-stationary streaming kernel where it applies (option conv2d_variant 16 switches it off,
+    // 17 takes it for small problems too)
+    if (plain && (g_opt.conv2d_variant == 0 || g_opt.conv2d_variant == 17)) {
+        const hipError_t e = launch_conv2d_stream(x, wgt, y, N, Cin, H, W, Cout, Ho, Wo, kh, kw, ph, pw, s, taken, wadj);
+        if (*taken || e != hipSuccess) return e;
+    }
     ConvGeom g;
     g.Cin = (int)Cin; g.H = (int)H; g.W = (int)W; g.Cout = (int)Cout; g.Ho = (int)Ho; g.Wo = (int)Wo;
     g.kh = kh; g.kw = kw; g.ph = ph; g.pw = pw; g.sh = sh; g.sw = sw; g.dh = dh; g.dw = dw;

@@ -136,6 +136,11 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
                               int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh,
                               int32_t sw, int32_t ph, int32_t pw, int32_t dh, int32_t dw, hipStream_t s,
                               bool *taken, int wadj = 0);
+// Weight-stationary streaming kernel (conv_stream.hip): 64 input channels, 3 x 3 on narrow images and
+// 1 x 3 on 1-D rows, stride 1; *taken = false: not its case, nothing launched.
+hipError_t launch_conv2d_stream(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H, int64_t W,
+                                int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t ph, int32_t pw,
+                                hipStream_t s, bool *taken, int wadj);
 // Strided adjoint with respect to the input, one stride-1 launch chain per output phase; phases no
 // tap reaches are NOT written (the caller clears gx first when kh < sh or kw < sw).
 hipError_t launch_conv2d_grad_input_phases(const float *gy, const float *wgt, float *gx, int64_t N, int64_t Cin,

@@ -313,6 +313,71 @@ def test_conv2d_integer_valued_bit_exact(B):
     assert np.array_equal(y.astype(np.float64), ref)
 
 
+STREAM_2D = [  # N, Cout, H, W, ph, pw
+    (2, 64, 20, 20, 1, 1), (1, 64, 56, 56, 1, 1), (3, 64, 7, 9, 1, 1), (2, 64, 33, 62, 1, 1), (1, 128, 12, 40, 0, 0),
+    (2, 64, 5, 30, 2, 2), (1, 64, 3, 3, 1, 1), (5, 128, 14, 14, 1, 0), (1, 64, 1, 60, 1, 1), (4, 64, 9, 31, 0, 1),
+    (1, 64, 40, 5, 2, 0), (37, 64, 6, 6, 1, 1)]
+
+
+@pytest.mark.parametrize("geom", STREAM_2D)
+def test_streaming_kernel_3x3(B, geom):
+    """The weight-stationary streaming kernel (64 input channels, 3 x 3, stride 1), forced on small problems
+    (option conv2d_variant 17): images narrower and wider than a position block, blocks that span several
+    rows, several images and output-channel tiles per run, every padding below the kernel size, runs that
+    are empty.  Integer-valued data in the same call: every fp32 partial sum is exact, so the result must
+    equal the oracle's bit for bit whatever the order of the four partial sums."""
+    n, cout, h, w, ph, pw = geom
+    r = _rng(sum(geom) * 7 + h)
+    x = r.standard_normal((n, 64, h, w), dtype=np.float32)
+    wt = (r.standard_normal((cout, 64, 3, 3), dtype=np.float32) * 0.06).astype(np.float32)
+    xi = workloads.integer_valued((n, 64, h, w), -4, 4, seed=h * w)
+    wi = workloads.integer_valued((cout, 64, 3, 3), -3, 3, seed=cout)
+    B.sws_set_option("conv2d_variant", 17)
+    try:
+        _c2(B, x, wt, 1, 1, ph, pw, what="stream 3x3 %s" % (geom,))
+        y = to_host(B.sws_conv2d(to_gpu(xi), to_gpu(wi), 1, 1, ph, pw))
+    finally:
+        B.sws_set_option("conv2d_variant", 0)
+    ref, _ = oracle.conv2d(xi, wi, 1, 1, ph, pw)
+    assert np.array_equal(y.astype(np.float64), ref), "stream 3x3 integer-valued %s" % (geom,)
+
+
+@pytest.mark.parametrize("geom", [(2, 64, 34, 0), (1, 64, 500, 1), (3, 128, 1000, 2), (16, 64, 4096, 0), (5, 64, 3, 1),
+                                  (1, 64, 66, 1), (2, 64, 32, 1), (7, 64, 95, 2)])
+def test_streaming_kernel_1d(B, geom):
+    """The same kernel on 1-D rows (1 x 3): lines are 32-column chunks of the padded row."""
+    n, cout, length, pad = geom
+    r = _rng(sum(geom) + 3)
+    x = r.standard_normal((n, 64, length), dtype=np.float32)
+    wt = (r.standard_normal((cout, 64, 3), dtype=np.float32) * 0.1).astype(np.float32)
+    xi = workloads.integer_valued((n, 64, length), -4, 4, seed=length)
+    wi = workloads.integer_valued((cout, 64, 3), -3, 3, seed=cout + 1)
+    B.sws_set_option("conv2d_variant", 17)
+    try:
+        _c1(B, x, wt, pad=pad, what="stream 1x3 %s" % (geom,))
+        y = to_host(B.sws_conv1d(to_gpu(xi), to_gpu(wi), 1, pad))
+    finally:
+        B.sws_set_option("conv2d_variant", 0)
+    ref, _ = oracle.conv1d(xi, wi, 1, pad)
+    assert np.array_equal(y.astype(np.float64), ref), "stream 1x3 integer-valued %s" % (geom,)
+
+
+def test_streaming_kernel_against_tile_kernel_full_size(B):
+    """cfg 4 on both matrix-core kernels (option 16 switches the streaming one off): both within tolerance of
+    the oracle, and of each other."""
+    x, w = workloads.make(4)
+    ref, mag = oracle.conv2d(x, w, 1, 1, 1, 1)
+    xg, wg = to_gpu(x), to_gpu(w)
+    ys = to_host(B.sws_conv2d(xg, wg, 1, 1, 1, 1))
+    B.sws_set_option("conv2d_variant", 16)
+    try:
+        yt = to_host(B.sws_conv2d(xg, wg, 1, 1, 1, 1))
+    finally:
+        B.sws_set_option("conv2d_variant", 0)
+    assert_within_tol(ys, ref, mag, "cfg4 streaming kernel")
+    assert_within_tol(yt, ref, mag, "cfg4 tile kernel")
+
+
 def test_cfg1_correlation_full_size(B):
     """N = 1,048,576, 5-tap correlation."""
     x, w = workloads.make(1)
