@@ -156,8 +156,8 @@ template <> struct SegStep<SWS_OP_MIN> {
 // MODE 0: plain rows.  MODE 1: rows extended by a boundary rule.  MODE 2: one link of a chain of
 // windows (see launch_chain): rows `pitch` apart of which `len` elements are used, results
 // combined with what an earlier link left in y.
-template <int OP, int C, int MODE>
-__global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__restrict__ x,
+template <int OP, int C, int MODE, int WPW = kWavesPerWg>
+__global__ __launch_bounds__(WPW * kWave) void slide_scan_kernel(const float *__restrict__ x,
                                                               float *__restrict__ y, int len, int lo, int S,
                                                               float scale, int tiles_per_row, int tout,
                                                               int group, int64_t n_tiles, int64_t n_units,
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
     constexpr int N = kWave * C;                    // inputs per wave tile
     constexpr int NS = C / 4;                       // 256-element strips per tile
     constexpr int REGION = N;
-    __shared__ __attribute__((aligned(16))) float lds[kWavesPerWg * 2 * REGION];
+    __shared__ __attribute__((aligned(16))) float lds[WPW * 2 * REGION];
 
     // kernel flag bits: 2 = non-temporal stores, 4 = aligned tile origins, 32 = workgroups keep
     // their launch order instead of the XCD-contiguous mapping
@@ -240,7 +240,7 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
     const int strip_pos = lds_pos(4 * lane);
     const int pre_pos0 = lds_pos(4 * (lane + s4)), pre_pos1 = lds_pos(4 * (lane + s4 + 1));
 
-    for (; gt < gt_end; gt += kWavesPerWg) {
+    for (; gt < gt_end; gt += WPW) {
         const float *xr = x + r * (int64_t)pitch;
         // With aligned tiles the origin is pulled back so that (r*lo + t0) is a multiple of 16
         // floats: every 1 KB strip store then starts on a 64-byte line.  The first tile of a row
@@ -383,7 +383,7 @@ __global__ __launch_bounds__(kThreads) void slide_scan_kernel(const float *__res
             }
         }
         wave_lds_sync();                                         // the next tile overwrites A
-        t += kWavesPerWg;
+        t += WPW;
         while (t >= tiles_per_row) { t -= tiles_per_row; ++r; }
     }
 }
@@ -460,9 +460,19 @@ hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, 
     // (For + the first form stays ahead up to w = 170 — x[32768,16384], w = 80 .. 160: 5.98-6.08 TB/s
     // against 5.5-5.7 — while max / min already prefer the second from w = 80 on: 5.7-5.94 against 5.6-5.85.)
     const bool one_tile = S <= 64 || (OP == SWS_OP_ADD && S <= 172);
-    int64_t g = one_tile ? kWavesPerWg : 2 * kWavesPerWg;
+    // Nothing ties the four wavefronts of a workgroup together (no barrier, private LDS slices), and
+    // single-wavefront workgroups measure a little faster on large plain inputs where the halo is
+    // small or the scan is the slower one (x[32768,16384], TB/s, one / four wavefronts: w = 16 + 6.05 /
+    // 5.94, max 5.98 / 5.92; w = 64 equal; w = 255 max 5.87 / 5.77, + with one tile per workgroup in
+    // launch order 6.10 / 5.90).  Option slide_chunk bit 64 forces them, bit 128 the four-wavefront shape.
+    const bool plain = !chain && lv == len;
+    const bool big = rows * (int64_t)tiles >= 16384;
+    const bool single = plain && !(opt & 128) && ((opt & 64) || (big && (S <= 32 || S > 172)));
+    const int wpw = single ? 1 : kWavesPerWg;
+    int64_t g = one_tile ? wpw : 2 * wpw;
     bool remap = one_tile;
-    if (g_opt.slide_group > 0) g = (g_opt.slide_group + kWavesPerWg - 1) / kWavesPerWg * kWavesPerWg;
+    if (single && OP == SWS_OP_ADD && S > 172) g = 1;
+    if (g_opt.slide_group > 0) g = (g_opt.slide_group + wpw - 1) / wpw * wpw;
     if (opt & 4) remap = true;
     if (opt & 8) remap = false;
     if (!remap) flags |= 32;
@@ -480,6 +490,9 @@ hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, 
     } else if (lv != len) {
         hipLaunchKernelGGL((slide_scan_kernel<OP, C, 1>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
                            S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, pad_left, pad_mode, lv);
+    } else if (single) {
+        hipLaunchKernelGGL((slide_scan_kernel<OP, C, 0, 1>), dim3((unsigned)grid), dim3(kWave), 0, s, x, y, len, lo,
+                           S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, 0, 0, len);
     } else {
         hipLaunchKernelGGL((slide_scan_kernel<OP, C, 0>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
                            S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, 0, 0, len);
