@@ -63,7 +63,7 @@ struct StreamGeom {
 __device__ __forceinline__ int fdiv(int x, float inv_d) { return (int)(((float)x + 0.5f) * inv_d); }
 
 // CGS = log2 of the 16-column groups per line, rounded up to a power of two (0 .. 2)
-template <int CIN, int KH, int KW, bool MODE_B, int CGS>
+template <int CIN, int KH, int KW, bool MODE_B, int CGS, bool WADJ>
 __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__restrict__ x,
                                                                const float *__restrict__ wgt,
                                                                float *__restrict__ y, StreamGeom g)
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
 #pragma unroll 1
         for (int h = 0; h < 2; ++h) {
             v4f v[PER];
-            if (g.wadj) {
+            if (WADJ) {
                 // stored as wgt[ci][co][KT - 1 - t] with rows of Cout pairs: for every ci the half tile is one
                 // contiguous range of 32 * KT floats; it is copied as it is (lane = output channel then
                 // reads addresses 9 floats apart: conflict-free)
@@ -224,9 +224,9 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const int ci = wq * CQ + cb * 8 + 4 * half + j;
-                        const float *rd = g.wadj ? wl + ci * (32 * KT) + l32 * KT : wl + l32 * WP + ci * KT;
+                        const float *rd = WADJ ? wl + ci * (32 * KT) + l32 * KT : wl + l32 * WP + ci * KT;
 #pragma unroll
-                        for (int t = 0; t < KT; ++t) w[t][cb][j] = rd[g.wadj ? KT - 1 - t : t];
+                        for (int t = 0; t < KT; ++t) w[t][cb][j] = rd[WADJ ? KT - 1 - t : t];
                     }
             }
         }
@@ -352,8 +352,8 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
         constexpr int I_COM = 0, I_ISS = 2, I_FIN = STEPS >= 7 ? 4 : 0, I_ADR = STEPS >= 7 ? 6 : 1, I_BAS = STEPS - 1;
         static_assert(STEPS >= 4 && STEPS > DEPTH, "room for the pieces between the groups");
         v4f bq[DEPTH + 1];
-        v4f fsum = {0.0f, 0.0f, 0.0f, 0.0f};
         float *y_cur = y;
+        int t_k3 = k3, t_n3 = n3, t_ct3 = ct3, t_base3 = base3, t_q3 = q3, t_r3 = r3, t_need3 = need3;
         auto bread = [&](int i) {
             const int t = i / NCB, cb = i % NCB;
             const int ofs = MODE_B ? cb * 32 : (t % KW) * PITCH * 4 + cb * 32;      // an instruction immediate
@@ -378,14 +378,20 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
             if (i == I_ISS + 1 && issue_now) issue(xr0, n0r, p0r, H2, XS);
             if (i == I_FIN && have_prev) {            // the previous block: the other quarters' partial sums
                 const v4f *sp = sc_rd + (buf ^ 1) * (2 * 4 * 3 * 64);
-                fsum = sp[0] + sp[64] + sp[128];
+                const v4f f = sp[0] + sp[64] + sp[128];
+                mine[0] += f.x; mine[1] += f.y; mine[2] += f.z; mine[3] += f.w;
             }
             if (i == I_FIN + 1 && have_prev && pok_prev) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) y_prev[(long long)q * HoWo] = mine[q] + fsum[q];
+                for (int q = 0; q < 4; ++q) y_prev[(long long)q * HoWo] = mine[q];
             }
             // accumulator register 4 wq + i is output channel 8 wq + 4 half + i of my block of 32
-            if (i == I_ADR) y_cur = y + ((long long)n * g.Cout + ct * 64) * HoWo + co_off + pp;
+            if (i == I_ADR) {
+                y_cur = y + ((long long)n * g.Cout + ct * 64) * HoWo + co_off + pp;
+                // scalar bookkeeping for the step after the next, here where it costs no matrix time
+                advance(t_k3, t_n3, t_ct3, t_base3, t_q3, t_r3);
+                t_need3 = gb + 3 < b1 ? t_base3 + hi_of(t_k3, t_q3) : need3;
+            }
             // after the last read of this block: the next block's tap addresses
             if (i == I_BAS) {
                 pok_prev = pok;
@@ -419,8 +425,8 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
         k = k2; n = n2; ct = ct2; img_base = base2;
         k2 = k3; n2 = n3; ct2 = ct3; base2 = base3; q2 = q3; r2 = r3;
         need2 = need3;
-        advance(k3, n3, ct3, base3, q3, r3);
-        need3 = gb + 3 < b1 ? base3 + hi_of(k3, q3) : need2;
+        k3 = t_k3; n3 = t_n3; ct3 = t_ct3; base3 = t_base3; q3 = t_q3; r3 = t_r3;
+        need3 = t_need3;
     }
     }
     finish(buf ^ 1);
@@ -440,20 +446,28 @@ int device_cus()
     return cus;
 }
 
-template <int CIN, int KH, int KW, bool MODE_B, int CGS>
-hipError_t launch_stream(const float *x, const float *wgt, float *y, const StreamGeom &g, size_t lds, int grid,
+template <int CIN, int KH, int KW, bool MODE_B, int CGS, bool WADJ>
+hipError_t launch_stream1(const float *x, const float *wgt, float *y, const StreamGeom &g, size_t lds, int grid,
                          hipStream_t s)
 {
     static bool raised = false;                       // (set once per process; the attribute is per function)
     if (!raised && lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute((const void *)conv_stream_kernel<CIN, KH, KW, MODE_B, CGS>,
+        const hipError_t e = hipFuncSetAttribute((const void *)conv_stream_kernel<CIN, KH, KW, MODE_B, CGS, WADJ>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((conv_stream_kernel<CIN, KH, KW, MODE_B, CGS>), dim3((unsigned)grid), dim3(kThreads), lds, s, x, wgt,
+    hipLaunchKernelGGL((conv_stream_kernel<CIN, KH, KW, MODE_B, CGS, WADJ>), dim3((unsigned)grid), dim3(kThreads), lds, s, x, wgt,
                        y, g);
     return hipGetLastError();
+}
+
+template <int CIN, int KH, int KW, bool MODE_B, int CGS>
+hipError_t launch_stream(const float *x, const float *wgt, float *y, const StreamGeom &g, size_t lds, int grid,
+                         hipStream_t s)
+{
+    if (g.wadj) return launch_stream1<CIN, KH, KW, MODE_B, CGS, true>(x, wgt, y, g, lds, grid, s);
+    return launch_stream1<CIN, KH, KW, MODE_B, CGS, false>(x, wgt, y, g, lds, grid, s);
 }
 
 }  // namespace
