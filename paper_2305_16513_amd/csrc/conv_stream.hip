@@ -349,7 +349,7 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
         constexpr int STEPS = KT * NCB, DEPTH = 2;
-        constexpr int I_COM = 0, I_ISS = 2, I_FIN = STEPS >= 7 ? 4 : 0, I_ADR = STEPS >= 7 ? 6 : 1, I_BAS = STEPS - 1;
+        constexpr int I_COM = 0, I_ISS = 2, I_FIN = STEPS >= 7 ? 4 : 0, I_ADR = STEPS >= 7 ? 6 : 1, I_BAS = STEPS - 1 - DEPTH;
         static_assert(STEPS >= 4 && STEPS > DEPTH, "room for the pieces between the groups");
         v4f bq[DEPTH + 1];
         float *y_cur = y;
@@ -392,7 +392,7 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
                 advance(t_k3, t_n3, t_ct3, t_base3, t_q3, t_r3);
                 t_need3 = gb + 3 < b1 ? t_base3 + hi_of(t_k3, t_q3) : need3;
             }
-            // after the last read of this block: the next block's tap addresses
+            // after the last read of this block has been issued: the next block's tap addresses
             if (i == I_BAS) {
                 pok_prev = pok;
                 if (more) bases(k2, base2, rb, pok, pp);
@@ -400,16 +400,21 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
             __builtin_amdgcn_sched_barrier(0);
         }
 
-        // ---- hand the three quarters I do not own to their owners; keep mine
-#pragma unroll
-        for (int dq = 0; dq < 4; ++dq) {
-            const v4f q4 = {acc[4 * dq], acc[4 * dq + 1], acc[4 * dq + 2], acc[4 * dq + 3]};
-            if (dq == wq) {
-                mine[0] = q4.x; mine[1] = q4.y; mine[2] = q4.z; mine[3] = q4.w;
-            } else {
-                const int src = (wq - dq - 1) & 3;    // 0 .. 2
-                sc_wr[buf * (2 * 4 * 3 * 64) + (dq * 3 + src) * 64] = q4;
-            }
+        // ---- hand the three quarters I do not own to their owners; keep mine.  Quarter (wq + 1 + j) & 3 lists
+        // me as its source 2 - j, so the three addresses are wave constants; which accumulator registers go
+        // where depends on wq: one branch over four short copies of the code.
+        {
+            v4f *wr = sc_wr + buf * (2 * 4 * 3 * 64);
+#define SWS_HAND(Q0, Q1, Q2, Q3)                                                                    \
+    mine[0] = acc[4 * Q0]; mine[1] = acc[4 * Q0 + 1]; mine[2] = acc[4 * Q0 + 2]; mine[3] = acc[4 * Q0 + 3];       \
+    wr[(Q1 * 3 + 2) * 64] = (v4f){acc[4 * Q1], acc[4 * Q1 + 1], acc[4 * Q1 + 2], acc[4 * Q1 + 3]};                \
+    wr[(Q2 * 3 + 1) * 64] = (v4f){acc[4 * Q2], acc[4 * Q2 + 1], acc[4 * Q2 + 2], acc[4 * Q2 + 3]};                \
+    wr[(Q3 * 3 + 0) * 64] = (v4f){acc[4 * Q3], acc[4 * Q3 + 1], acc[4 * Q3 + 2], acc[4 * Q3 + 3]}
+            if (wq == 0) { SWS_HAND(0, 1, 2, 3); }
+            else if (wq == 1) { SWS_HAND(1, 2, 3, 0); }
+            else if (wq == 2) { SWS_HAND(2, 3, 0, 1); }
+            else { SWS_HAND(3, 0, 1, 2); }
+#undef SWS_HAND
         }
         y_prev = y_cur;
         have_prev = true;
