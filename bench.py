@@ -284,6 +284,17 @@ def sweeps_table(torch, B, workloads, iters=20):
                     "Gelem_per_s": round(ROWS5 * (LEN5 - w + 1) / ms / 1e6, 1)}
                 del y
         del xs
+    # configuration 5's depthwise layer on bf16 storage (fp32 taps and arithmetic, one rounding)
+    taps = g(workloads.make(5, x_shape=(1, 128, 64))[1])
+    k5 = taps.shape[-1]
+    x16 = x16.view(256, 128, LEN5)
+    y = torch.empty(256, 128, LEN5 - k5 + 1, device="cuda", dtype=torch.bfloat16)
+    ms = time_launches(torch, lambda: B.sws_conv1d_16(x16, taps, groups=128, y=y), iters)
+    nb = slide_bytes(ROWS5, LEN5, k5) // 2
+    out["storage_16bit"]["bf16_depthwise_conv_k%d" % k5] = {
+        "ms": round(ms, 4), "GBps": round(nb / ms / 1e6, 1), "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4),
+        "Gelem_per_s": round(ROWS5 * (LEN5 - k5 + 1) / ms / 1e6, 1)}
+    del y, taps
     del x16
     torch.cuda.empty_cache()
     x3 = g(workloads.make(3)[0]).to(torch.bfloat16)       # configuration 3's pooling on bf16 storage
@@ -480,6 +491,12 @@ def run_only(torch, B, workloads, name, steps, cold=False):
         x = g(workloads.make(5)[0]).to(dt)
         y = torch.empty(256, 128, LEN5 - w + 1, device="cuda", dtype=dt)
         fn = lambda: B.sws_slide1d_16(0 if opn == "add" else 1, x, w, 1.0 / w, y=y)
+    elif name == "dwconv16_k31":                          # the depthwise layer on bf16 storage
+        x_host, taps_host = workloads.make(5)
+        x = g(x_host).to(torch.bfloat16)
+        taps = g(taps_host)
+        y = torch.empty(256, 128, LEN5 - K5 + 1, device="cuda", dtype=torch.bfloat16)
+        fn = lambda: B.sws_conv1d_16(x, taps, groups=CH5, y=y)
     elif name.startswith("slide_") or name == "dwconv_k31":
         x_host, taps_host = workloads.make(5)
         x = g(x_host)
@@ -569,10 +586,8 @@ def run_only(torch, B, workloads, name, steps, cold=False):
         fn = lambda: B.sws_conv1d(x6, taps, y=y)
     else:
         raise SystemExit("bench.py --only: unknown operator %r" % name)
-    for _ in range(steps):
-        fn()
-    torch.cuda.synchronize()
-    print(json.dumps({"only": name, "launches": steps, "cold": bool(cold)}))
+    ms = time_launches(torch, fn, steps, warm=2)
+    print(json.dumps({"only": name, "launches": steps, "cold": bool(cold), "ms_per_launch": round(ms, 5)}))
 
 
 def cpu_baseline(x_host, taps_host):

@@ -204,6 +204,20 @@ sws_status sws_conv1d(const float *x, const float *wgt, float *y, int64_t B, int
                       int64_t L, int64_t Cout, int32_t k, int32_t stride, int32_t pad,
                       int32_t dilation, int32_t groups, void *stream);
 
+/* sws_conv1d on 16-bit storage (the paper's introduction names quantisation as the way to shrink
+ * what a layer moves; Section 2.5 itself is unchanged): x and y hold bf16 or fp16 elements, the taps
+ * stay fp32.  Each element is widened to fp32 exactly, the sliding dot product is accumulated in
+ * fp32 as in sws_conv1d, and each output is rounded to the storage type once, to nearest even.
+ * The depthwise layer (groups = Cin = Cout, stride 1, dilation 1, k <= 64), which is bound by
+ * memory traffic, moves half the bytes of the fp32 entry point; other geometries are evaluated
+ * directly.
+ *   x : device [B,Cin,L] 16-bit    wgt : device [Cout,Cin/groups,k] fp32    y : device [B,Cout,Lo] 16-bit
+ *   (x, y 2-byte aligned, wgt 4-byte aligned; densely packed)
+ * Errors: as sws_conv1d, and INVALID_ARG for an unknown dtype. */
+sws_status sws_conv1d_16(sws_dtype dtype, const void *x, const float *wgt, void *y, int64_t B, int64_t Cin,
+                         int64_t L, int64_t Cout, int32_t k, int32_t stride, int32_t pad, int32_t dilation,
+                         int32_t groups, void *stream);
+
 /* The two adjoints of sws_conv1d (the training side of the sliding dot product of Section 2.5;
  * the abstract names training next to inference).  With loss = sum(gy * y):
  *

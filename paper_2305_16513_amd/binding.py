@@ -19,7 +19,7 @@ _lib = None
 
 _i64, _i32, _f32, _vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
 
-EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_maxpool2d_grad", "sws_avgpool2d_grad", "sws_pool2d_16", "sws_pool2d_ex", "sws_conv1d", "sws_conv1d_grad_input", "sws_conv1d_grad_weight", "sws_conv2d", "sws_conv2d_grad_input", "sws_conv2d_grad_weight", "sws_copy", "sws_out_len",
+EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_maxpool2d_grad", "sws_avgpool2d_grad", "sws_pool2d_16", "sws_pool2d_ex", "sws_conv1d", "sws_conv1d_16", "sws_conv1d_grad_input", "sws_conv1d_grad_weight", "sws_conv2d", "sws_conv2d_grad_input", "sws_conv2d_grad_weight", "sws_copy", "sws_out_len",
            "sws_status_string", "sws_set_option", "sws_version")
 
 
@@ -61,6 +61,8 @@ def lib():
                                     _i32, _i32, _i32, _i32, ctypes.c_int, _f32, _vp]
         L.sws_conv1d.restype = ctypes.c_int
         L.sws_conv1d.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _vp]
+        L.sws_conv1d_16.restype = ctypes.c_int
+        L.sws_conv1d_16.argtypes = [ctypes.c_int, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _vp]
         for f in (L.sws_conv1d_grad_input, L.sws_conv1d_grad_weight):
             f.restype = ctypes.c_int
             f.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _vp]
@@ -295,6 +297,31 @@ def sws_conv1d(x, wgt, stride=1, pad=0, dilation=1, groups=1, y=None, stream=Non
     y = _out(y, (b, cout, lo), x)
     _check(lib().sws_conv1d(x.data_ptr(), wgt.data_ptr(), y.data_ptr(), b, cin, length, cout, k, stride,
                             pad, dilation, groups, _stream(stream)), "sws_conv1d")
+    return y
+
+
+def sws_conv1d_16(x, wgt, stride=1, pad=0, dilation=1, groups=1, y=None, stream=None):
+    """x [B, Cin, L] of bfloat16 or float16, wgt [Cout, Cin/groups, k] fp32 -> y [B, Cout, Lo] of x's type."""
+    if not isinstance(x, torch.Tensor) or not x.is_cuda:
+        raise TypeError("x must be a GPU tensor")
+    if x.dtype not in _DTYPE_16 or not x.is_contiguous() or x.dim() != 3:
+        raise TypeError("x must be contiguous bfloat16 or float16 of shape [B, Cin, L]")
+    _dev(wgt, "wgt")
+    b, cin, length = x.shape
+    cout, cig, k = wgt.shape
+    if cig * groups != cin:
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_conv1d_16")
+    lo = sws_out_len(length, k, stride, pad, dilation)
+    if lo < 1:
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_conv1d_16")
+    shape = (b, cout, lo)
+    if y is None:
+        y = torch.empty(shape, dtype=x.dtype, device=x.device)
+    elif (not isinstance(y, torch.Tensor) or not y.is_cuda or y.dtype != x.dtype or not y.is_contiguous()
+          or tuple(y.shape) != shape):
+        raise TypeError("y must be a contiguous GPU tensor of x's type and shape %s" % (shape,))
+    _check(lib().sws_conv1d_16(_DTYPE_16[x.dtype], x.data_ptr(), wgt.data_ptr(), y.data_ptr(), b, cin, length, cout,
+                               k, stride, pad, dilation, groups, _stream(stream)), "sws_conv1d_16")
     return y
 
 

@@ -249,6 +249,26 @@ sws_status sws_conv1d(const float *x, const float *wgt, float *y, int64_t B, int
                                        (hipStream_t)stream));
 }
 
+sws_status sws_conv1d_16(sws_dtype dtype, const void *x, const float *wgt, void *y, int64_t B, int64_t Cin, int64_t L,
+                         int64_t Cout, int32_t k, int32_t stride, int32_t pad, int32_t dilation, int32_t groups,
+                         void *stream)
+{
+    if (dtype != SWS_DTYPE_BF16 && dtype != SWS_DTYPE_F16) return SWS_ERR_INVALID_ARG;
+    if (B < 0 || Cin < 1 || L < 0 || Cout < 1 || k < 1 || stride < 1 || pad < 0 || dilation < 1 || groups < 1)
+        return SWS_ERR_INVALID_ARG;
+    if (Cin % groups || Cout % groups || L > kMaxDim || Cin > kMaxDim || Cout > kMaxDim)
+        return SWS_ERR_INVALID_ARG;
+    const int64_t Lo = sws_out_len(L, k, stride, pad, dilation);
+    if (Lo < 1) return SWS_ERR_INVALID_ARG;
+    int64_t n_in, n_out, n_w;
+    if (!mul3(B, Cin, L, &n_in) || !mul3(B, Cout, Lo, &n_out) || !mul3(Cout, Cin / groups, k, &n_w))
+        return SWS_ERR_INVALID_ARG;
+    if (B == 0) return SWS_OK;
+    if (!x || !wgt || !y) return SWS_ERR_INVALID_ARG;
+    return from_hip(sws::launch_conv1d_16((int)dtype, x, wgt, y, B, Cin, L, Cout, Lo, k, stride, pad, dilation, groups,
+                                          (hipStream_t)stream));
+}
+
 namespace {
 
 // Shared argument checks of the convolution and its adjoints; *Lo receives the output length.

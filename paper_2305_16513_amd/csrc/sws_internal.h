@@ -114,6 +114,10 @@ hipError_t launch_pool2d_16(int op, int dtype, const void *x, void *y, int64_t p
 hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin, int64_t L,
                          int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad,
                          int32_t dilation, int32_t groups, hipStream_t s, int wadj = 0, bool *taken = nullptr);
+// 16-bit storage (conv1d16.hip): x, y bf16 / fp16, taps fp32.
+hipError_t launch_conv1d_16(int dtype, const void *x, const float *wgt, void *y, int64_t B, int64_t Cin, int64_t L,
+                            int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad, int32_t dilation,
+                            int32_t groups, hipStream_t s);
 // Adjoints of the 1-D convolution (conv_grad.hip).
 hipError_t launch_conv1d_grad_input(const float *gy, const float *wgt, float *gx, int64_t B, int64_t Cin, int64_t L,
                                     int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad,

@@ -199,3 +199,17 @@ def test_new_entry_points_argument_checks(L):
     assert L.sws_pool2d_16(0, 1, one, one, 0, 3, 8, 8, 3, 3, 1, 1, 1, 1, 1.0, nul) == 0
     assert L.sws_pool2d_16(0, 3, one, one, 1, 3, 8, 8, 3, 3, 1, 1, 1, 1, 1.0, nul) == 1
     assert L.sws_pool2d_16(0, 1, one, nul, 1, 3, 8, 8, 3, 3, 1, 1, 1, 1, 1.0, nul) == 1
+
+
+def test_conv1d_16_argument_checks(L):
+    one, nul = ctypes.c_void_p(16), ctypes.c_void_p(0)
+    i64, i32 = ctypes.c_int64, ctypes.c_int32
+    L.sws_conv1d_16.argtypes = [ctypes.c_int] + [ctypes.c_void_p] * 3 + [i64] * 4 + [i32] * 5 + [ctypes.c_void_p]
+    c = lambda **kw: L.sws_conv1d_16(*[kw.get(n, v) for n, v in zip(
+        ("dtype", "x", "w", "y", "B", "Cin", "L", "Cout", "k", "stride", "pad", "dil", "groups", "s"),
+        (1, one, one, one, 1, 4, 32, 4, 3, 1, 0, 1, 4, nul))])
+    assert c(B=0) == 0
+    assert c(dtype=0) == 1 and c(dtype=3) == 1                             # fp32 / unknown storage type
+    assert c(groups=3) == 1 and c(k=0) == 1 and c(k=33) == 1 and c(stride=0) == 1 and c(dil=0) == 1 and c(pad=-1) == 1
+    assert c(x=nul) == 1 and c(w=nul) == 1 and c(y=nul) == 1
+    assert c(L=2 ** 31) == 1
