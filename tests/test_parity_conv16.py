@@ -29,11 +29,17 @@ def B():
     binding.sws_set_option("slide_group", 0)
 
 
-def _check(B, kind, x32, wgt, what, min_exact=0.99, **geom):
-    """x32 [B, Cin, L] float32 host array, rounded to the storage type here (input preparation)."""
+def _check(B, kind, x32, wgt, what, min_exact=0.99, variant=0, **geom):
+    """x32 [B, Cin, L] float32 host array, rounded to the storage type here (input preparation).
+    variant: 0 the library's choice (matrix-core kernel for depthwise layers), 1 direct evaluation,
+    2 the vector-ALU depthwise kernel."""
     tdt, odt, half_step = TYPES[kind]
     xq = torch.from_numpy(np.ascontiguousarray(x32)).to(tdt)               # the data both sides read
-    y = B.sws_conv1d_16(xq.cuda(), torch.from_numpy(wgt).cuda(), **geom)
+    B.sws_set_option("conv1d_variant", variant)
+    try:
+        y = B.sws_conv1d_16(xq.cuda(), torch.from_numpy(wgt).cuda(), **geom)
+    finally:
+        B.sws_set_option("conv1d_variant", 0)
     assert y.dtype == tdt
     got = y.cpu().to(torch.float64).numpy()
     ref, mag = oracle.conv1d(xq.to(torch.float32).numpy(), wgt, **geom)    # exact widening
@@ -55,23 +61,26 @@ def _data(shape_x, shape_w, seed):
     return x, w
 
 
+@pytest.mark.parametrize("variant", [0, 2])
 @pytest.mark.parametrize("kind", ["bf16", "f16"])
-@pytest.mark.parametrize("k", [1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 31, 32, 33, 47, 48, 63, 64])
-def test_depthwise_every_tap_count(B, kind, k):
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 18, 31, 32, 33, 34, 47, 48, 49, 50, 63, 64])
+def test_depthwise_every_tap_count(B, kind, k, variant):
     """Depthwise rows of odd length (every row after the first starts on an odd 2-byte boundary, so
     no strip load is aligned) spanning several 1024-output tiles and a ragged tail."""
     x, w = _data((2, 3, 5003), (3, 1, k), 300 + k)
-    _check(B, kind, x, w, "%s depthwise k=%d" % (kind, k), groups=3)
+    _check(B, kind, x, w, "%s depthwise k=%d variant %d" % (kind, k, variant), variant=variant, groups=3)
 
 
+@pytest.mark.parametrize("variant", [0, 2])
 @pytest.mark.parametrize("kind", ["bf16", "f16"])
 @pytest.mark.parametrize("length,k,pad", [(1, 1, 0), (2, 2, 0), (5, 5, 2), (9, 3, 1), (17, 16, 15), (31, 31, 0),
                                           (64, 64, 63), (255, 7, 3), (1023, 31, 15), (1024, 31, 15), (1025, 2, 1),
                                           (1054, 31, 0), (1055, 31, 0), (2047, 64, 0), (2048, 5, 4), (3000, 33, 32)])
-def test_depthwise_short_rows_and_padding(B, kind, length, k, pad):
+def test_depthwise_short_rows_and_padding(B, kind, length, k, pad, variant):
     """Rows shorter than a tile, rows that end right at a tile edge, zero padding up to k-1."""
     x, w = _data((3, 5, length), (5, 1, k), 11 * length + k)
-    _check(B, kind, x, w, "%s len=%d k=%d pad=%d" % (kind, length, k, pad), min_exact=0.97, groups=5, pad=pad)
+    _check(B, kind, x, w, "%s len=%d k=%d pad=%d variant %d" % (kind, length, k, pad, variant), min_exact=0.97,
+           variant=variant, groups=5, pad=pad)
 
 
 @pytest.mark.parametrize("kind", ["bf16", "f16"])
@@ -81,14 +90,16 @@ def test_channel_multiplier(B, kind):
     _check(B, kind, x, w, kind + " multiplier 2", groups=4, pad=4)
 
 
+@pytest.mark.parametrize("variant", [0, 2])
 @pytest.mark.parametrize("kind", ["bf16", "f16"])
 @pytest.mark.parametrize("group", [1, 3, 4, 9])
-def test_chunking_of_a_row(B, kind, group):
-    """The row is cut into chunks of `group` tiles per workgroup: every split must give the same outputs."""
+def test_chunking_of_a_row(B, kind, group, variant):
+    """The row is cut into runs of `group` tiles per work unit: every split must give the same outputs.
+    (7 rows: the last workgroup of the matrix-core kernel has idle wavefronts.)"""
     B.sws_set_option("slide_group", group)
     try:
-        x, w = _data((1, 2, 20011), (2, 1, 31), 5 + group)
-        _check(B, kind, x, w, "%s group=%d" % (kind, group), groups=2, pad=7)
+        x, w = _data((1, 7, 20011), (7, 1, 31), 5 + group)
+        _check(B, kind, x, w, "%s group=%d variant %d" % (kind, group, variant), variant=variant, groups=7, pad=7)
     finally:
         B.sws_set_option("slide_group", 0)
 
@@ -110,14 +121,10 @@ def test_general_geometries(B, kind, geom):
 
 
 @pytest.mark.parametrize("kind", ["bf16", "f16"])
-def test_both_kernels_agree_with_the_oracle_on_the_same_layer(B, kind):
+def test_all_kernels_agree_with_the_oracle_on_the_same_layer(B, kind):
     x, w = _data((2, 3, 4100), (3, 1, 31), 41)
-    for variant in (0, 1):
-        B.sws_set_option("conv1d_variant", variant)
-        try:
-            _check(B, kind, x, w, "%s variant %d" % (kind, variant), groups=3, pad=15)
-        finally:
-            B.sws_set_option("conv1d_variant", 0)
+    for variant in (0, 1, 2):
+        _check(B, kind, x, w, "%s variant %d" % (kind, variant), variant=variant, groups=3, pad=15)
 
 
 @pytest.mark.parametrize("kind", ["bf16", "f16"])
@@ -125,20 +132,36 @@ def test_exact_on_small_integers(B, kind):
     """Integer taps and data: every product and partial sum is exact in fp32 and the results are
     representable in the storage type, so any summation order must reproduce the oracle's bits."""
     tdt = TYPES[kind][0]
-    for k, pad in ((3, 1), (8, 0), (31, 15)):
-        x = workloads.integer_valued((2, 4, 3001), -2, 2, seed=k)
-        w = workloads.integer_valued((4, 1, k), -1, 1, seed=100 + k)
-        y = B.sws_conv1d_16(torch.from_numpy(x).to(tdt).cuda(), torch.from_numpy(w).cuda(), pad=pad, groups=4)
-        ref, _ = oracle.conv1d(x, w, pad=pad, groups=4)
-        assert np.abs(ref).max() <= 256
-        assert np.array_equal(y.cpu().to(torch.float64).numpy(), ref)
+    for variant in (0, 2):
+        for k, pad in ((3, 1), (8, 0), (31, 15), (64, 0)):
+            x = workloads.integer_valued((2, 4, 3001), -2, 2, seed=k)
+            w = workloads.integer_valued((4, 1, k), -1, 1, seed=100 + k)
+            B.sws_set_option("conv1d_variant", variant)
+            try:
+                y = B.sws_conv1d_16(torch.from_numpy(x).to(tdt).cuda(), torch.from_numpy(w).cuda(), pad=pad, groups=4)
+            finally:
+                B.sws_set_option("conv1d_variant", 0)
+            ref, _ = oracle.conv1d(x, w, pad=pad, groups=4)
+            assert np.abs(ref).max() <= 256
+            assert np.array_equal(y.cpu().to(torch.float64).numpy(), ref), "variant %d k=%d" % (variant, k)
 
 
 @pytest.mark.parametrize("kind", ["bf16", "f16"])
-def test_layer_shaped_rows(B, kind):
+@pytest.mark.parametrize("variant", [0, 2])
+def test_layer_shaped_rows(B, kind, variant):
     """A slab of the headline depthwise layer: 128 channels of 16384 elements, 31 taps, 2 images."""
     x, w = workloads.make(5, x_shape=(2, 128, 16384))
-    _check(B, kind, x, w, kind + " cfg5 slab", groups=128)
+    _check(B, kind, x, w, "%s cfg5 slab variant %d" % (kind, variant), variant=variant, groups=128)
+
+
+@pytest.mark.parametrize("kind", ["bf16", "f16"])
+def test_taps_that_need_all_three_pieces(B, kind):
+    """Taps with 24 significant bits and a wide spread of magnitudes (1e-6 .. 10) on data of mixed
+    magnitude: the matrix-core kernel must carry every bit of every tap."""
+    rng = np.random.Generator(np.random.PCG64(77))
+    w = (rng.standard_normal((6, 1, 31)) * 10.0 ** rng.uniform(-6, 1, (6, 1, 31))).astype(np.float32)
+    x = (rng.standard_normal((2, 6, 3000)) * 10.0 ** rng.uniform(-3, 1, (2, 6, 3000))).astype(np.float32)
+    _check(B, kind, x, w, kind + " wide taps", min_exact=0.985, groups=6)
 
 
 def test_output_guard_band(B):
