@@ -257,7 +257,7 @@ __device__ __forceinline__ void split_half2(unsigned w, unsigned &hi, unsigned &
 
 // NCH: 16-wide slices of s that a block of 32 outputs reads: 31 + k <= 16 * NCH.
 template <int NCH, int PF, typename T>
-__global__ __launch_bounds__(kThreads) void conv1d16_mfma_kernel(
+__global__ __launch_bounds__(kThreads, (NCH <= 4 ? 4 : 3)) void conv1d16_mfma_kernel(
     const T *__restrict__ x, const float *__restrict__ wgt, T *__restrict__ y, int L, int Lo, int k, int pad, int Cin,
     int Cout, int cog, int tiles_per_row, int group, int chunks_per_row, int64_t n_wave_units)
 {
@@ -487,12 +487,11 @@ hipError_t conv1d_16(const T *x, const float *wgt, T *y, int64_t B, int64_t Cin,
     if (thin_ok && g_opt.conv1d_variant != 2) {
         const int cog = (int)(Cout / groups);
         hipError_t e = hipErrorInvalidValue;
-        const int pf = g_opt.slide_chunk;            // tiles in flight ahead of the arithmetic (A/B): 1, 2, else 3
+        const int pf = g_opt.slide_chunk;            // tiles in flight ahead of the arithmetic: 2 (A/B: 1)
 #define SWS_MFMA16(N)                                                                                           \
     case N:                                                                                                     \
-        e = pf == 1   ? launch_mfma16<N, 1, T>(x, wgt, y, B * Cout, (int)L, (int)Lo, k, pad, (int)Cin, (int)Cout, cog, s) \
-            : pf == 2 ? launch_mfma16<N, 2, T>(x, wgt, y, B * Cout, (int)L, (int)Lo, k, pad, (int)Cin, (int)Cout, cog, s) \
-                      : launch_mfma16<N, 3, T>(x, wgt, y, B * Cout, (int)L, (int)Lo, k, pad, (int)Cin, (int)Cout, cog, s); \
+        e = pf == 1 ? launch_mfma16<N, 1, T>(x, wgt, y, B * Cout, (int)L, (int)Lo, k, pad, (int)Cin, (int)Cout, cog, s) \
+                    : launch_mfma16<N, 2, T>(x, wgt, y, B * Cout, (int)L, (int)Lo, k, pad, (int)Cin, (int)Cout, cog, s); \
         break
         switch ((31 + k + 15) / 16) {
             SWS_MFMA16(2); SWS_MFMA16(3); SWS_MFMA16(4); SWS_MFMA16(5); SWS_MFMA16(6);

@@ -27,6 +27,7 @@ def B():
     yield binding
     binding.sws_set_option("conv1d_variant", 0)
     binding.sws_set_option("slide_group", 0)
+    binding.sws_set_option("slide_chunk", 0)
 
 
 def _check(B, kind, x32, wgt, what, min_exact=0.99, variant=0, **geom):
@@ -102,6 +103,18 @@ def test_chunking_of_a_row(B, kind, group, variant):
         _check(B, kind, x, w, "%s group=%d variant %d" % (kind, group, variant), variant=variant, groups=7, pad=7)
     finally:
         B.sws_set_option("slide_group", 0)
+
+
+@pytest.mark.parametrize("kind", ["bf16", "f16"])
+@pytest.mark.parametrize("k", [3, 31, 40, 64])
+def test_one_tile_in_flight(B, kind, k):
+    """The matrix-core kernel with a single tile of loads ahead of the arithmetic (A/B knob)."""
+    B.sws_set_option("slide_chunk", 1)
+    try:
+        x, w = _data((2, 3, 7001), (3, 1, k), 60 + k)
+        _check(B, kind, x, w, "%s k=%d one tile ahead" % (kind, k), groups=3, pad=k // 2)
+    finally:
+        B.sws_set_option("slide_chunk", 0)
 
 
 @pytest.mark.parametrize("kind", ["bf16", "f16"])
