@@ -12,16 +12,25 @@
  *     aligned bases are fastest).  Inputs are read-only and must not overlap
  *     the output.  The library allocates nothing, frees nothing and keeps no
  *     pointer after the call returns.
- *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - `stream` is a hipStream_t (sws_stream_t is the same pointer type, declared
+ *     here so that the header needs no HIP include; NULL = the default stream).
  *     Work is enqueued on it; calls are asynchronous and never synchronise.
  *   - Errors are reported by return code only.  Arguments are checked before
  *     anything is launched; a problem with zero outputs returns SWS_OK without
- *     launching.  A failed launch returns SWS_ERR_HIP.
+ *     launching.  A failed launch returns SWS_ERR_HIP; the thread's HIP
+ *     last-error state is cleared on entry, so that an error left by earlier
+ *     calls of the caller is not reported as a failure of this one.
  *   - Inputs are assumed finite.  NaN propagation through MAX / MIN is
  *     unspecified, and so is the sign of a zero result when a MAX / MIN window
- *     holds both +0.0 and -0.0.
- *   - Reentrant; no mutable global state except the developer knobs of
- *     sws_set_option().
+ *     holds both +0.0 and -0.0.  ADD and the convolutions accumulate in fp32:
+ *     once a partial sum of a window (or of the up to 2w elements around it
+ *     that a scan segment covers) overflows fp32, the outputs near it are
+ *     unspecified (inf or NaN), even where the window's own sum is finite.
+ *   - Row lengths and plane extents are indexed in int32: at most
+ *     2^31 - 1 - 65536 = 2147418111 elements ("the int32 limit" below).
+ *   - Reentrant: the entry points of this header keep no mutable global state.
+ *     (The measurement knobs of sws_dev.h are process-wide and are not part of
+ *     this contract.)
  */
 #ifndef SWS_H
 #define SWS_H
@@ -31,6 +40,10 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+
+/* hipStream_t is `struct ihipStream_t *` in <hip/hip_runtime_api.h>; a caller that includes the HIP
+ * headers passes its hipStream_t unchanged. */
+typedef struct ihipStream_t *sws_stream_t;
 
 typedef enum {
     SWS_OK = 0,
@@ -63,9 +76,9 @@ typedef enum {
  *   x : device, rows*len floats          y : device, rows*(len-w+1) floats
  *   scale multiplies ADD results (1/w gives 1-D average pooling); ignored for MAX / MIN.
  * Errors: INVALID_ARG if op is unknown, rows < 0, len < 0, w < 1, w > len, a pointer is
- * NULL while there is output, or a size overflows int64 / len exceeds 2^31-1. */
+ * NULL while there is output, or a size overflows int64 / len exceeds the int32 limit. */
 sws_status sws_slide1d(sws_op op, const float *x, float *y, int64_t rows, int64_t len,
-                       int32_t w, float scale, void *stream);
+                       int32_t w, float scale, sws_stream_t stream);
 
 /* The same sliding window sum over rows extended by pad_left virtual elements in front and
  * pad_right behind, filled by the boundary rule `mode`:
@@ -80,7 +93,7 @@ sws_status sws_slide1d(sws_op op, const float *x, float *y, int64_t rows, int64_
  * pad is not smaller than w. */
 sws_status sws_slide1d_padded(sws_op op, const float *x, float *y, int64_t rows, int64_t len,
                               int32_t w, int32_t pad_left, int32_t pad_right, sws_pad_mode mode,
-                              float scale, void *stream);
+                              float scale, sws_stream_t stream);
 
 /* Storage types of sws_slide1d_16.  Arithmetic is fp32 for both. */
 typedef enum {
@@ -98,7 +111,7 @@ typedef enum {
  *   (2-byte aligned; densely packed)
  * Errors: as sws_slide1d, and INVALID_ARG for an unknown dtype. */
 sws_status sws_slide1d_16(sws_op op, sws_dtype dtype, const void *x, void *y, int64_t rows,
-                          int64_t len, int32_t w, float scale, void *stream);
+                          int64_t len, int32_t w, float scale, sws_stream_t stream);
 
 /* Sliding window sum (Eq. 3) under the pair operator of Section 2.4, Eq. 8 — the associative,
  * NON-commutative operator with which the paper writes a dot product as a prefix sum:
@@ -110,9 +123,9 @@ sws_status sws_slide1d_16(sws_op op, sws_dtype dtype, const void *x, void *y, in
  * planes.  u = 1 gives the sliding add of v; v = 0 gives the sliding product of u.
  *   u, v : device, rows*len floats each        yu, yv : device, rows*(len-w+1) floats each
  * Errors: INVALID_ARG if rows < 0, len < 0, w < 1, w > len, a pointer is NULL while there is
- * output, or a size overflows int64 / len exceeds 2^31-1. */
+ * output, or a size overflows int64 / len exceeds the int32 limit. */
 sws_status sws_slide1d_pair(const float *u, const float *v, float *yu, float *yv, int64_t rows,
-                            int64_t len, int32_t w, void *stream);
+                            int64_t len, int32_t w, sws_stream_t stream);
 
 /* 2-D pooling (Section 2.3 extended to two dimensions) evaluated as separable sliding
  * sums, first along H then along W, on NCHW data:
@@ -125,10 +138,10 @@ sws_status sws_slide1d_pair(const float *u, const float *v, float *yu, float *yv
  *   x : device, N*C*H*W floats          y : device, N*C*Ho*Wo floats
  * Errors: INVALID_ARG for unknown op, negative sizes, kh/kw/sh/sw < 1, ph/pw < 0,
  * ph >= kh or pw >= kw (a window wholly inside padding), window larger than the padded
- * input, NULL pointer with output, H or W above 2^31-1. */
+ * input, NULL pointer with output, H or W above the int32 limit. */
 sws_status sws_pool2d(sws_op op, const float *x, float *y, int64_t N, int64_t C, int64_t H,
                       int64_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
-                      int32_t ph, int32_t pw, float scale, void *stream);
+                      int32_t ph, int32_t pw, float scale, sws_stream_t stream);
 
 /* The adjoint of max pooling (sws_pool2d with SWS_OP_MAX, same geometry) at the point x: with
  * loss = sum(gy * y), every window adds its gy to the gx of the cell that holds its maximum — the
@@ -139,7 +152,7 @@ sws_status sws_pool2d(sws_op op, const float *x, float *y, int64_t N, int64_t C,
  * Errors: as sws_pool2d. */
 sws_status sws_maxpool2d_grad(const float *x, const float *gy, float *gx, int64_t N, int64_t C,
                               int64_t H, int64_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
-                              int32_t ph, int32_t pw, void *stream);
+                              int32_t ph, int32_t pw, sws_stream_t stream);
 
 /* sws_pool2d on 16-bit storage, defined like sws_slide1d_16: x and y hold bf16 or fp16 elements,
  * each widened to fp32 exactly; the window is combined in fp32 as in sws_pool2d, multiplied by
@@ -148,7 +161,7 @@ sws_status sws_maxpool2d_grad(const float *x, const float *gy, float *gx, int64_
  * Errors: as sws_pool2d, and INVALID_ARG for an unknown dtype. */
 sws_status sws_pool2d_16(sws_op op, sws_dtype dtype, const void *x, void *y, int64_t N, int64_t C,
                          int64_t H, int64_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
-                         int32_t ph, int32_t pw, float scale, void *stream);
+                         int32_t ph, int32_t pw, float scale, sws_stream_t stream);
 
 /* What an ADD result of sws_pool2d_ex is divided by. */
 typedef enum {
@@ -172,7 +185,7 @@ typedef enum {
 sws_status sws_pool2d_ex(sws_op op, const float *x, float *y, int64_t N, int64_t C, int64_t H,
                          int64_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
                          int32_t pad_top, int32_t pad_left, int32_t pad_bottom, int32_t pad_right,
-                         sws_divisor divisor, float scale, void *stream);
+                         sws_divisor divisor, float scale, sws_stream_t stream);
 
 /* The adjoint of average pooling (Section 2.3's pooling with the + operator, training side): of
  * sws_pool2d_ex with SWS_OP_ADD, padding ph on top and bottom and pw left and right, and the same
@@ -186,7 +199,7 @@ sws_status sws_pool2d_ex(sws_op op, const float *x, float *y, int64_t N, int64_t
  * Errors: as sws_pool2d; INVALID_ARG for an unknown divisor. */
 sws_status sws_avgpool2d_grad(const float *gy, float *gx, int64_t N, int64_t C, int64_t H, int64_t W,
                               int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
-                              sws_divisor divisor, float scale, void *stream);
+                              sws_divisor divisor, float scale, sws_stream_t stream);
 
 /* 1-D convolution as a sliding dot product (Section 2.5; Eq. 4 per output), in the DNN
  * sense: cross-correlation, taps not flipped, zero padding, no bias.
@@ -199,10 +212,10 @@ sws_status sws_avgpool2d_grad(const float *gy, float *gx, int64_t N, int64_t C, 
  * groups = 1 is the dense-channel contraction; groups = Cin = Cout is depthwise.
  * Errors: INVALID_ARG for sizes < 0, Cin/Cout/k/stride/dilation/groups < 1, pad < 0,
  * Cin or Cout not divisible by groups, kernel span above the padded length, NULL pointer
- * with output, L above 2^31-1. */
+ * with output, L above the int32 limit. */
 sws_status sws_conv1d(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin,
                       int64_t L, int64_t Cout, int32_t k, int32_t stride, int32_t pad,
-                      int32_t dilation, int32_t groups, void *stream);
+                      int32_t dilation, int32_t groups, sws_stream_t stream);
 
 /* sws_conv1d on 16-bit storage (the paper's introduction names quantisation as the way to shrink
  * what a layer moves; Section 2.5 itself is unchanged): x and y hold bf16 or fp16 elements, the taps
@@ -216,7 +229,7 @@ sws_status sws_conv1d(const float *x, const float *wgt, float *y, int64_t B, int
  * Errors: as sws_conv1d, and INVALID_ARG for an unknown dtype. */
 sws_status sws_conv1d_16(sws_dtype dtype, const void *x, const float *wgt, void *y, int64_t B, int64_t Cin,
                          int64_t L, int64_t Cout, int32_t k, int32_t stride, int32_t pad, int32_t dilation,
-                         int32_t groups, void *stream);
+                         int32_t groups, sws_stream_t stream);
 
 /* The two adjoints of sws_conv1d (the training side of the sliding dot product of Section 2.5;
  * the abstract names training next to inference).  With loss = sum(gy * y):
@@ -234,10 +247,10 @@ sws_status sws_conv1d_16(sws_dtype dtype, const void *x, const float *wgt, void 
  * Errors: as sws_conv1d. */
 sws_status sws_conv1d_grad_input(const float *gy, const float *wgt, float *gx, int64_t B,
                                  int64_t Cin, int64_t L, int64_t Cout, int32_t k, int32_t stride,
-                                 int32_t pad, int32_t dilation, int32_t groups, void *stream);
+                                 int32_t pad, int32_t dilation, int32_t groups, sws_stream_t stream);
 sws_status sws_conv1d_grad_weight(const float *x, const float *gy, float *gw, int64_t B,
                                   int64_t Cin, int64_t L, int64_t Cout, int32_t k, int32_t stride,
-                                  int32_t pad, int32_t dilation, int32_t groups, void *stream);
+                                  int32_t pad, int32_t dilation, int32_t groups, sws_stream_t stream);
 
 /* 2-D convolution (same reading of Section 2.5 on NCHW x and OIHW wgt, groups = 1):
  *
@@ -248,7 +261,7 @@ sws_status sws_conv1d_grad_weight(const float *x, const float *gy, float *gw, in
  * Errors: as sws_conv1d. */
 sws_status sws_conv2d(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin,
                       int64_t H, int64_t W, int64_t Cout, int32_t kh, int32_t kw,
-                      int32_t sh, int32_t sw, int32_t ph, int32_t pw, void *stream);
+                      int32_t sh, int32_t sw, int32_t ph, int32_t pw, sws_stream_t stream);
 
 /* The two adjoints of sws_conv2d, defined like those of sws_conv1d (loss = sum(gy * y)):
  *   gx[n,ci,h,c]     = sum over (co, a, b) with h + ph - a = ho*sh, c + pw - b = wo*sw inside the
@@ -262,16 +275,16 @@ sws_status sws_conv2d(const float *x, const float *wgt, float *y, int64_t N, int
 sws_status sws_conv2d_grad_input(const float *gy, const float *wgt, float *gx, int64_t N,
                                  int64_t Cin, int64_t H, int64_t W, int64_t Cout, int32_t kh,
                                  int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
-                                 void *stream);
+                                 sws_stream_t stream);
 sws_status sws_conv2d_grad_weight(const float *x, const float *gy, float *gw, int64_t N,
                                   int64_t Cin, int64_t H, int64_t W, int64_t Cout, int32_t kh,
                                   int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
-                                  void *stream);
+                                  sws_stream_t stream);
 
 /* Plain device-to-device copy of n floats with the same 128-bit access pattern the
  * sliding kernels use.  Not part of the method: it measures the HBM ceiling a
  * one-read-one-write kernel can reach on this device, and calibrates byte counters. */
-sws_status sws_copy(const float *src, float *dst, int64_t n, void *stream);
+sws_status sws_copy(const float *src, float *dst, int64_t n, sws_stream_t stream);
 
 /* Host helper: number of outputs of a sliding window of `w` taps spaced `dilation`
  * apart over `len` inputs padded by `pad` on both sides, moved in steps of `stride`.
@@ -280,12 +293,6 @@ int64_t sws_out_len(int64_t len, int32_t w, int32_t stride, int32_t pad, int32_t
 
 /* Static, never-freed description of a status code. */
 const char *sws_status_string(int status);
-
-/* Developer knobs for A/B measurements (not needed for normal use; not thread-safe).
- * Known keys: "slide_variant", "pool2d_variant", "conv1d_variant", "conv2d_variant",
- * "copy_variant" (0 = automatic choice), "slide_chunk" (tiling / store-policy bits) and
- * "slide_group" (tiles per workgroup).  Returns SWS_ERR_INVALID_ARG for an unknown key. */
-sws_status sws_set_option(const char *key, int64_t value);
 
 /* Library version, "major.minor". */
 const char *sws_version(void);

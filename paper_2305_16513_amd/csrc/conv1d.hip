@@ -179,7 +179,7 @@ hipError_t launch_thin(const float *x, const float *wgt, float *y, int64_t rows_
     const int group = (tiles_per_row + chunks_per_row - 1) / chunks_per_row;     // even chunks
     const int64_t n_units = rows_out * chunks_per_row;
     const int64_t grid = xcd_grid(n_units);
-    if (grid > 2147483647LL) return hipErrorInvalidValue;
+    if (grid > 2147483647LL) return kNotTaken;
     hipLaunchKernelGGL((conv1d_thin_kernel<KB4>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, wgt, y, L, Lo, k,
                        pad, Cin, Cout, cog, tiles_per_row, group, chunks_per_row, n_units, wflip);
     return hipGetLastError();
@@ -483,7 +483,7 @@ hipError_t launch_thin_dilated(const float *x, const float *wgt, float *y, int64
     const int group = (tiles_per_row + chunks_per_row - 1) / chunks_per_row;     // even chunks
     const int64_t n_units = rows_out * chunks_per_row;
     const int64_t grid = xcd_grid(n_units);
-    if (grid > 2147483647LL) return hipErrorInvalidValue;
+    if (grid > 2147483647LL) return kNotTaken;
     const size_t lds_bytes = ((size_t)pl.tab_strips * 256 + (size_t)kWavesPerWg * pl.slice) * sizeof(float);
 #define SWS_DIL_LAUNCH(MULTI, STRIDED)                                                                          \
     hipLaunchKernelGGL((conv1d_thin_dilated_kernel<KB4, MULTI, STRIDED>), dim3((unsigned)grid), dim3(kThreads),  \
@@ -606,7 +606,7 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
             pc.wadj = wadj;
             pc.accum = c > 0;
             const int pad_c = pad - first * dilation;           // the chunk's first tap sits first * dilation further on
-            hipError_t e = hipErrorInvalidValue;
+            hipError_t e = kNotTaken;
 #define SWS_THIN_DIL(KB)                                                                                        \
     case KB:                                                                                                    \
         e = launch_thin_dilated<KB>(x, wgt, y, B * Cout, (int)L, (int)Lo, kc, pad_c, pc, (int)Cin, (int)Cout, cog,  \

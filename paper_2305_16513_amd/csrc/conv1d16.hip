@@ -208,7 +208,7 @@ hipError_t launch_thin16(const T *x, const float *wgt, T *y, int64_t rows_out, i
     const int group = (tiles_per_row + chunks_per_row - 1) / chunks_per_row;     // even chunks
     const int64_t n_units = rows_out * chunks_per_row;
     const int64_t grid = xcd_grid(n_units);
-    if (grid > 2147483647LL) return hipErrorInvalidValue;
+    if (grid > 2147483647LL) return kNotTaken;
     hipLaunchKernelGGL((conv1d16_thin_kernel<KB4, T>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, wgt, y, L, Lo, k,
                        pad, Cin, Cout, cog, tiles_per_row, group, chunks_per_row, n_units);
     return hipGetLastError();
@@ -444,7 +444,7 @@ hipError_t launch_mfma16(const T *x, const float *wgt, T *y, int64_t rows_out, i
     const int group = (tiles_per_row + chunks_per_row - 1) / chunks_per_row;     // even chunks
     const int64_t n_wave_units = rows_out * chunks_per_row;
     const int64_t grid = xcd_grid((n_wave_units + kWavesPerWg - 1) / kWavesPerWg);
-    if (grid > 2147483647LL) return hipErrorInvalidValue;
+    if (grid > 2147483647LL) return kNotTaken;
     hipLaunchKernelGGL((conv1d16_mfma_kernel<NCH, PF, T>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, wgt, y, L, Lo, k,
                        pad, Cin, Cout, cog, tiles_per_row, group, chunks_per_row, n_wave_units);
     return hipGetLastError();
@@ -486,7 +486,7 @@ hipError_t conv1d_16(const T *x, const float *wgt, T *y, int64_t B, int64_t Cin,
     const bool thin_ok = cig == 1 && stride == 1 && dilation == 1 && k <= kThinMaxK16 && g_opt.conv1d_variant != 1;
     if (thin_ok && g_opt.conv1d_variant != 2) {
         const int cog = (int)(Cout / groups);
-        hipError_t e = hipErrorInvalidValue;
+        hipError_t e = kNotTaken;
         const int pf = g_opt.slide_chunk;            // tiles in flight ahead of the arithmetic: 2 (A/B: 1)
 #define SWS_MFMA16(N)                                                                                           \
     case N:                                                                                                     \
@@ -498,10 +498,10 @@ hipError_t conv1d_16(const T *x, const float *wgt, T *y, int64_t B, int64_t Cin,
         default: break;
         }
 #undef SWS_MFMA16
-        if (e != hipErrorInvalidValue) return e;     // (a grid beyond the launch limit falls through)
+        if (e != kNotTaken) return e;     // (a grid beyond the launch limit falls through)
     } else if (thin_ok) {
         const int cog = (int)(Cout / groups);
-        hipError_t e = hipErrorInvalidValue;
+        hipError_t e = kNotTaken;
 #define SWS_THIN16(KB)                                                                                          \
     case KB:                                                                                                    \
         e = launch_thin16<KB, T>(x, wgt, y, B * Cout, (int)L, (int)Lo, k, pad, (int)Cin, (int)Cout, cog, s);    \
@@ -513,7 +513,7 @@ hipError_t conv1d_16(const T *x, const float *wgt, T *y, int64_t B, int64_t Cin,
         default: break;
         }
 #undef SWS_THIN16
-        if (e != hipErrorInvalidValue) return e;     // (a grid beyond the launch limit falls through)
+        if (e != kNotTaken) return e;     // (a grid beyond the launch limit falls through)
     }
     int64_t grid = (B * Cout * Lo + kThreads - 1) / kThreads;
     if (grid > 1048576) grid = 1048576;

@@ -438,7 +438,7 @@ hipError_t launch_thin_gw(const float *x, const float *gy, float *gw, int B, int
     int bgroup = (64 + tiles_per_row - 1) / tiles_per_row;
     while (bgroup > 1 && (int64_t)Cout * ((B + bgroup - 1) / bgroup) < 2048) bgroup = (bgroup + 1) / 2;
     const int64_t n_units = (int64_t)Cout * ((B + bgroup - 1) / bgroup);
-    if (n_units > 2147483647LL) return hipErrorInvalidValue;
+    if (n_units > 2147483647LL) return kNotTaken;
     hipLaunchKernelGGL((conv1d_thin_grad_weight_kernel<KB4>), dim3((unsigned)n_units), dim3(kThreads), 0, s, x, gy, gw,
                        B, Cin, L, Cout, Lo, k, pad, cog, tiles_per_row, bgroup, n_units);
     return hipGetLastError();
@@ -636,7 +636,7 @@ hipError_t launch_conv2d_grad_weight(const float *x, const float *gy, float *gw,
                                      int32_t sw, int32_t ph, int32_t pw, hipStream_t s)
 {
     const int64_t n_gw = Cout * Cin * kh * kw;
-    if (n_gw > 2147483647LL) return hipErrorInvalidValue;
+    if (n_gw > 2147483647LL) return kNotTaken;
     if (N > 0 && sw <= 2 && Cin >= 2 && g_opt.conv2d_variant != 1 && H * W <= 2147483647LL && Ho * Wo <= 2147483647LL) {
         int64_t fg = (n_gw + kThreads - 1) / kThreads;
         if (fg > 4096) fg = 4096;
@@ -700,7 +700,7 @@ hipError_t launch_conv1d_grad_weight(const float *x, const float *gy, float *gw,
     const int cig = (int)(Cin / groups), cog = (int)(Cout / groups);
     const int64_t n_gw = Cout * cig * k;
     const int variant = g_opt.conv1d_variant;        // 1 forces direct evaluation (A/B and tests)
-    if (n_gw > 2147483647LL) return hipErrorInvalidValue;
+    if (n_gw > 2147483647LL) return kNotTaken;
     const bool thin_ok = B > 0 && cig == 1 && stride == 1 && dilation == 1 && k <= 64 && B <= 2147483647LL && variant != 1;
     const bool dense_ok = B > 0 && groups == 1 && stride <= 2 && Cin >= 2 && variant != 1;
     if (thin_ok || dense_ok) {

@@ -528,7 +528,7 @@ hipError_t launch(const float *x, const float *wgt, float *y, const ConvGeom &g,
                   hipStream_t s)
 {
     const int64_t grid = xcd_grid(n_units);
-    if (grid > 2147483647LL) return hipErrorInvalidValue;
+    if (grid > 2147483647LL) return kNotTaken;
     hipLaunchKernelGGL((conv2d_mfma_kernel<WAVES, MB, NBW, CIB>), dim3((unsigned)grid), dim3(WAVES * 64), lds_bytes,
                        s, x, wgt, y, g, n_units);
     return hipGetLastError();

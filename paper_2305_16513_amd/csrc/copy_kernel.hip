@@ -55,12 +55,12 @@ hipError_t launch_copy(const float *src, float *dst, int64_t n, hipStream_t s)
 {
     if (g_opt.copy_variant == 4) {                   // one 1 KB strip per single-wavefront workgroup
         const int64_t fine = (n + 255) / 256;
-        if (fine > 2147483647LL) return hipErrorInvalidValue;
+        if (fine > 2147483647LL) return kNotTaken;
         if (fine > 0) hipLaunchKernelGGL(copy_fine_kernel, dim3((unsigned)fine), dim3(64), 0, s, src, dst, n);
         return hipGetLastError();
     }
     const int64_t grid = (n + 4095) / 4096;
-    if (grid > 2147483647LL) return hipErrorInvalidValue;
+    if (grid > 2147483647LL) return kNotTaken;
     // copy_variant: 0 non-temporal loads and stores (the fastest copy measured: 6.07 TB/s on 2 GiB),
     // 1 plain both (5.73), 3 plain loads + non-temporal stores, as the sliding kernels do (5.75),
     // 4 the fine-grained copy above

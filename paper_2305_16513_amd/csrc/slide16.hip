@@ -393,7 +393,7 @@ hipError_t launch_16_direct_w(const T *x, T *y, int64_t rows, int len, int lo, f
     const int rows_per_wg = strips < kWave ? kWave / strips : 1;
     const int recip = 65536 / strips + 1;
     const int64_t grid = rows_per_wg == 1 ? rows * wg_per_row : (rows + rows_per_wg - 1) / rows_per_wg;
-    if (grid > 2147483647LL) return hipErrorInvalidValue;
+    if (grid > 2147483647LL) return kNotTaken;
     hipLaunchKernelGGL((slide16_direct_kernel<OP, T, W>), dim3((unsigned)grid), dim3(kWave), 0, s, x, y, rows, len, lo,
                        scale, strips, wg_per_row, rows_per_wg, recip, align);
     return hipGetLastError();
@@ -403,7 +403,7 @@ template <int OP, typename T, int W0>
 hipError_t launch_16_direct(const T *x, T *y, int64_t rows, int len, int lo, int w, float scale, hipStream_t s)
 {
     if constexpr (W0 > kDirectMaxW) {
-        return hipErrorInvalidValue;
+        return kNotTaken;
     } else {
         if (w == W0) return launch_16_direct_w<OP, T, W0>(x, y, rows, len, lo, scale, s);
         return launch_16_direct<OP, T, W0 + 1>(x, y, rows, len, lo, w, scale, s);
@@ -423,7 +423,7 @@ hipError_t launch_16(const T *x, T *y, int64_t rows, int len, int lo, int w, flo
     const bool direct_auto = w <= 9 || lo < 2048 || rows * (int64_t)len <= (1LL << 25);
     if (w <= kDirectMaxW && variant != 1 && (variant == 3 || w == 1 || (variant != 2 && direct_auto))) {
         const hipError_t e = launch_16_direct<OP, T, 1>(x, y, rows, len, lo, w, scale, s);
-        if (e != hipErrorInvalidValue) return e;     // a grid beyond the launch limit: the kernels below
+        if (e != kNotTaken) return e;     // a grid beyond the launch limit: the kernels below
     }
     if (w >= 2 && w <= kScanMaxW && variant != 1) {
         const int S = w - 1;
@@ -442,7 +442,7 @@ hipError_t launch_16(const T *x, T *y, int64_t rows, int len, int lo, int w, flo
         if (g_opt.slide_chunk & 8) remap = 0;
         const int64_t n_units = (n_tiles + g - 1) / g;
         const int64_t grid = remap ? xcd_grid(n_units) : n_units;
-        if (grid > 2147483647LL) return hipErrorInvalidValue;
+        if (grid > 2147483647LL) return kNotTaken;
         hipLaunchKernelGGL((slide16_scan_kernel<OP, T>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo, S,
                            scale, tiles, tout, (int)g, n_tiles, n_units, remap);
         return hipGetLastError();

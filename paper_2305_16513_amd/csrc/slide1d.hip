@@ -408,7 +408,7 @@ hipError_t launch_direct(const float *x, float *y, int64_t rows, int len, int lo
     // against 6.18 TB/s); slide_chunk bit 4 forces the mapping on, bit 8 off
     const int remap = (g_opt.slide_chunk & 8) ? 0 : ((g_opt.slide_chunk & 4) || !fine ? 1 : 0);
     const int64_t grid = remap ? xcd_grid(n_units) : n_units;
-    if (grid > 2147483647LL) return hipErrorInvalidValue;
+    if (grid > 2147483647LL) return kNotTaken;
 #define SWS_DIRECT(WV)                                                                                     \
     case WV:                                                                                               \
         if (fine)                                                                                          \
@@ -422,7 +422,7 @@ hipError_t launch_direct(const float *x, float *y, int64_t rows, int len, int lo
         SWS_DIRECT(1); SWS_DIRECT(2); SWS_DIRECT(3); SWS_DIRECT(4); SWS_DIRECT(5);
         SWS_DIRECT(6); SWS_DIRECT(7); SWS_DIRECT(8); SWS_DIRECT(9);
         SWS_DIRECT(10); SWS_DIRECT(11);
-    default: return hipErrorInvalidValue;
+    default: return kNotTaken;
     }
 #undef SWS_DIRECT
     return hipGetLastError();
@@ -478,7 +478,7 @@ hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, 
     if (!remap) flags |= 32;
     const int64_t n_units = (n_tiles + g - 1) / g;
     const int64_t grid = remap ? xcd_grid(n_units) : n_units;
-    if (grid > 2147483647LL) return hipErrorInvalidValue;
+    if (grid > 2147483647LL) return kNotTaken;
     if (chain & 8) {                                  // a link over extended rows (chain bits: 1 = combine with y, 2 = last)
         if (!(chain & 2)) flags &= ~2;
         hipLaunchKernelGGL((slide_scan_kernel<OP, C, 3>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
@@ -615,7 +615,7 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
     }
     if (variant == 7) {
         const hipError_t e = launch_slide1d_rows(op, x, y, rows, len, lo, w, scale, padded, pad_left, pad_mode, s);
-        if (e != hipErrorInvalidValue) return e;
+        if (e != kNotTaken) return e;
         variant = w == 1 ? (padded ? 1 : 2) : 3;     // a grid beyond the launch limit
     }
     if (variant == 1) return launch_slide1d_naive(op, x, y, rows, len64, w, pad_left, pad_right, pad_mode, scale, s);

@@ -301,7 +301,7 @@ hipError_t launch_generic_tiles(const float *x0, const float *x1, float *y0, flo
     const int64_t tiles_per_row = (lo + tout - 1) / tout;
     const int64_t n_tiles = rows * tiles_per_row;
     const int64_t grid = (n_tiles + waves - 1) / waves;
-    if (grid > 2147483647LL) return hipErrorInvalidValue;
+    if (grid > 2147483647LL) return kNotTaken;
     if (small)
         hipLaunchKernelGGL((slide_generic_kernel<O, 8>), dim3((unsigned)grid), dim3(256), 0, s, x0, x1, y0, y1, len, lo, S,
                            tout, (int)tiles_per_row, n_tiles, scale, 1.0f / (float)S, pitch, accum);
@@ -335,7 +335,7 @@ hipError_t launch_generic(const float *x0, const float *x1, float *y0, float *y1
         return hipSuccess;
     }
     const int64_t grid = (rows * lo + 255) / 256;
-    if (grid > 2147483647LL) return hipErrorInvalidValue;
+    if (grid > 2147483647LL) return kNotTaken;
     hipLaunchKernelGGL((slide_generic_direct_kernel<O>), dim3((unsigned)grid), dim3(256), 0, s, x0, x1, y0, y1, rows,
                        (int)len, (int)lo, w, scale);
     return hipGetLastError();

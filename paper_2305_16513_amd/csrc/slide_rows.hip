@@ -138,7 +138,7 @@ hipError_t launch_rows_w(const float *x, float *y, int64_t rows, int len, int lo
     const int rows_per_wg = strips < kWave ? kWave / strips : 1;
     const int recip = 65536 / strips + 1;
     const int64_t grid = rows_per_wg == 1 ? rows * wg_per_row : (rows + rows_per_wg - 1) / rows_per_wg;
-    if (grid > 2147483647LL) return hipErrorInvalidValue;
+    if (grid > 2147483647LL) return kNotTaken;
     if (padded)
         hipLaunchKernelGGL((slide_rows_kernel<OP, W, true>), dim3((unsigned)grid), dim3(kWave), 0, s, x, y, rows, len,
                            lo, scale, strips, wg_per_row, rows_per_wg, recip, pad_left, pad_mode);
@@ -153,7 +153,7 @@ hipError_t launch_rows(const float *x, float *y, int64_t rows, int len, int lo, 
                        int pad_left, int pad_mode, hipStream_t s)
 {
     if constexpr (W0 > kRowsMaxW) {
-        return hipErrorInvalidValue;
+        return kNotTaken;
     } else {
         if (w == W0) return launch_rows_w<OP, W0>(x, y, rows, len, lo, scale, padded, pad_left, pad_mode, s);
         return launch_rows<OP, W0 + 1>(x, y, rows, len, lo, w, scale, padded, pad_left, pad_mode, s);
@@ -165,12 +165,12 @@ hipError_t launch_rows(const float *x, float *y, int64_t rows, int len, int lo, 
 int slide1d_rows_max_w() { return kRowsMaxW; }
 
 // len: the physical row; lo: outputs per row (of the extended row when padded).
-// hipErrorInvalidValue: w beyond the kernel's reach or a grid beyond the launch limit (the caller
+// kNotTaken: w beyond the kernel's reach or a grid beyond the launch limit (the caller
 // then takes another kernel).
 hipError_t launch_slide1d_rows(int op, const float *x, float *y, int64_t rows, int len, int lo, int32_t w, float scale,
                                bool padded, int pad_left, int pad_mode, hipStream_t s)
 {
-    if (w < 1 || w > kRowsMaxW) return hipErrorInvalidValue;
+    if (w < 1 || w > kRowsMaxW) return kNotTaken;
     switch (op) {
     case SWS_OP_ADD: return launch_rows<SWS_OP_ADD, 1>(x, y, rows, len, lo, w, scale, padded, pad_left, pad_mode, s);
     case SWS_OP_MAX: return launch_rows<SWS_OP_MAX, 1>(x, y, rows, len, lo, w, scale, padded, pad_left, pad_mode, s);

@@ -4,7 +4,7 @@
 #include "sws_internal.h"
 
 namespace sws {
-Options g_opt = {0, 0, 0, 0, 0, 0, 0};
+Options g_opt;
 }
 
 namespace {
@@ -22,7 +22,14 @@ bool mul3(int64_t a, int64_t b, int64_t c, int64_t *out)
 
 bool valid_op(int op) { return op == SWS_OP_ADD || op == SWS_OP_MAX || op == SWS_OP_MIN; }
 
-sws_status from_hip(hipError_t e) { return e == hipSuccess ? SWS_OK : SWS_ERR_HIP; }
+// kNotTaken reaching the boundary: no kernel covers the request (a grid beyond the launch limit).
+sws_status from_hip(hipError_t e)
+{
+    return e == hipSuccess ? SWS_OK : e == sws::kNotTaken ? SWS_ERR_UNSUPPORTED : SWS_ERR_HIP;
+}
+// Launchers report hipGetLastError() after their launch; an error left over from the caller's earlier
+// HIP calls is cleared first so that it is not taken for a failure of this launch.
+#define SWS_LAUNCH(call) ((void)hipGetLastError(), from_hip(call))
 
 }  // namespace
 
@@ -65,16 +72,16 @@ sws_status sws_set_option(const char *key, int64_t value)
     return SWS_OK;
 }
 
-sws_status sws_copy(const float *src, float *dst, int64_t n, void *stream)
+sws_status sws_copy(const float *src, float *dst, int64_t n, sws_stream_t stream)
 {
     if (n < 0 || n > INT64_MAX / 4) return SWS_ERR_INVALID_ARG;
     if (n == 0) return SWS_OK;
     if (!src || !dst) return SWS_ERR_INVALID_ARG;
-    return from_hip(sws::launch_copy(src, dst, n, (hipStream_t)stream));
+    return SWS_LAUNCH(sws::launch_copy(src, dst, n, (hipStream_t)stream));
 }
 
 sws_status sws_slide1d(sws_op op, const float *x, float *y, int64_t rows, int64_t len, int32_t w,
-                       float scale, void *stream)
+                       float scale, sws_stream_t stream)
 {
     if (!valid_op((int)op) || rows < 0 || len < 0 || w < 1) return SWS_ERR_INVALID_ARG;
     if (len > kMaxDim || (int64_t)w > len) return SWS_ERR_INVALID_ARG;
@@ -82,11 +89,11 @@ sws_status sws_slide1d(sws_op op, const float *x, float *y, int64_t rows, int64_
     if (!mul3(rows, len, 1, &n_in)) return SWS_ERR_INVALID_ARG;
     if (rows == 0) return SWS_OK;
     if (!x || !y) return SWS_ERR_INVALID_ARG;
-    return from_hip(sws::launch_slide1d((int)op, x, y, rows, len, w, 0, 0, SWS_PAD_IDENTITY, scale, (hipStream_t)stream));
+    return SWS_LAUNCH(sws::launch_slide1d((int)op, x, y, rows, len, w, 0, 0, SWS_PAD_IDENTITY, scale, (hipStream_t)stream));
 }
 
 sws_status sws_slide1d_16(sws_op op, sws_dtype dtype, const void *x, void *y, int64_t rows, int64_t len, int32_t w,
-                          float scale, void *stream)
+                          float scale, sws_stream_t stream)
 {
     if (!valid_op((int)op) || rows < 0 || len < 0 || w < 1) return SWS_ERR_INVALID_ARG;
     if (dtype != SWS_DTYPE_BF16 && dtype != SWS_DTYPE_F16) return SWS_ERR_INVALID_ARG;
@@ -95,11 +102,11 @@ sws_status sws_slide1d_16(sws_op op, sws_dtype dtype, const void *x, void *y, in
     if (!mul3(rows, len, 1, &n_in)) return SWS_ERR_INVALID_ARG;
     if (rows == 0) return SWS_OK;
     if (!x || !y) return SWS_ERR_INVALID_ARG;
-    return from_hip(sws::launch_slide1d_16((int)op, (int)dtype, x, y, rows, len, w, scale, (hipStream_t)stream));
+    return SWS_LAUNCH(sws::launch_slide1d_16((int)op, (int)dtype, x, y, rows, len, w, scale, (hipStream_t)stream));
 }
 
 sws_status sws_slide1d_padded(sws_op op, const float *x, float *y, int64_t rows, int64_t len, int32_t w,
-                              int32_t pad_left, int32_t pad_right, sws_pad_mode mode, float scale, void *stream)
+                              int32_t pad_left, int32_t pad_right, sws_pad_mode mode, float scale, sws_stream_t stream)
 {
     if (!valid_op((int)op) || rows < 0 || len < 1 || w < 1 || pad_left < 0 || pad_right < 0) return SWS_ERR_INVALID_ARG;
     if ((int)mode < SWS_PAD_IDENTITY || (int)mode > SWS_PAD_SHRINK) return SWS_ERR_INVALID_ARG;
@@ -112,12 +119,12 @@ sws_status sws_slide1d_padded(sws_op op, const float *x, float *y, int64_t rows,
     if (!mul3(rows, lv, 1, &n_out)) return SWS_ERR_INVALID_ARG;
     if (rows == 0) return SWS_OK;
     if (!x || !y) return SWS_ERR_INVALID_ARG;
-    return from_hip(sws::launch_slide1d((int)op, x, y, rows, len, w, pad_left, pad_right, (int)mode, scale,
+    return SWS_LAUNCH(sws::launch_slide1d((int)op, x, y, rows, len, w, pad_left, pad_right, (int)mode, scale,
                                         (hipStream_t)stream));
 }
 
 sws_status sws_slide1d_pair(const float *u, const float *v, float *yu, float *yv, int64_t rows, int64_t len,
-                            int32_t w, void *stream)
+                            int32_t w, sws_stream_t stream)
 {
     if (rows < 0 || len < 0 || w < 1) return SWS_ERR_INVALID_ARG;
     if (len > kMaxDim || (int64_t)w > len) return SWS_ERR_INVALID_ARG;
@@ -125,12 +132,12 @@ sws_status sws_slide1d_pair(const float *u, const float *v, float *yu, float *yv
     if (!mul3(rows, len, 1, &n_in)) return SWS_ERR_INVALID_ARG;
     if (rows == 0) return SWS_OK;
     if (!u || !v || !yu || !yv) return SWS_ERR_INVALID_ARG;
-    return from_hip(sws::launch_slide1d_pair(u, v, yu, yv, rows, len, w, (hipStream_t)stream));
+    return SWS_LAUNCH(sws::launch_slide1d_pair(u, v, yu, yv, rows, len, w, (hipStream_t)stream));
 }
 
 sws_status sws_pool2d(sws_op op, const float *x, float *y, int64_t N, int64_t C, int64_t H, int64_t W,
                       int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
-                      float scale, void *stream)
+                      float scale, sws_stream_t stream)
 {
     if (!valid_op((int)op) || N < 0 || C < 0 || H < 0 || W < 0) return SWS_ERR_INVALID_ARG;
     if (kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0) return SWS_ERR_INVALID_ARG;
@@ -144,13 +151,13 @@ sws_status sws_pool2d(sws_op op, const float *x, float *y, int64_t N, int64_t C,
     if (H * W > kMaxDim) return SWS_ERR_UNSUPPORTED;
     if (planes == 0) return SWS_OK;
     if (!x || !y) return SWS_ERR_INVALID_ARG;
-    return from_hip(sws::launch_pool2d((int)op, x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, 0,
+    return SWS_LAUNCH(sws::launch_pool2d((int)op, x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale, 0,
                                        (hipStream_t)stream));
 }
 
 sws_status sws_avgpool2d_grad(const float *gy, float *gx, int64_t N, int64_t C, int64_t H, int64_t W, int32_t kh,
                               int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw, sws_divisor divisor, float scale,
-                              void *stream)
+                              sws_stream_t stream)
 {
     if (N < 0 || C < 0 || H < 0 || W < 0) return SWS_ERR_INVALID_ARG;
     if (kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0) return SWS_ERR_INVALID_ARG;
@@ -165,12 +172,12 @@ sws_status sws_avgpool2d_grad(const float *gy, float *gx, int64_t N, int64_t C, 
     if (H * W > kMaxDim) return SWS_ERR_UNSUPPORTED;
     if (planes == 0) return SWS_OK;
     if (!gy || !gx) return SWS_ERR_INVALID_ARG;
-    return from_hip(sws::launch_avgpool2d_grad(gy, gx, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw,
+    return SWS_LAUNCH(sws::launch_avgpool2d_grad(gy, gx, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw,
                                                divisor == SWS_DIV_REAL_CELLS ? 1 : 0, scale, (hipStream_t)stream));
 }
 
 sws_status sws_maxpool2d_grad(const float *x, const float *gy, float *gx, int64_t N, int64_t C, int64_t H, int64_t W,
-                              int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw, void *stream)
+                              int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw, sws_stream_t stream)
 {
     if (N < 0 || C < 0 || H < 0 || W < 0) return SWS_ERR_INVALID_ARG;
     if (kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0) return SWS_ERR_INVALID_ARG;
@@ -184,11 +191,11 @@ sws_status sws_maxpool2d_grad(const float *x, const float *gy, float *gx, int64_
     if (H * W > kMaxDim) return SWS_ERR_UNSUPPORTED;
     if (planes == 0) return SWS_OK;
     if (!x || !gy || !gx) return SWS_ERR_INVALID_ARG;
-    return from_hip(sws::launch_maxpool2d_grad(x, gy, gx, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, (hipStream_t)stream));
+    return SWS_LAUNCH(sws::launch_maxpool2d_grad(x, gy, gx, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, (hipStream_t)stream));
 }
 
 sws_status sws_pool2d_16(sws_op op, sws_dtype dtype, const void *x, void *y, int64_t N, int64_t C, int64_t H, int64_t W,
-                         int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw, float scale, void *stream)
+                         int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw, float scale, sws_stream_t stream)
 {
     if (!valid_op((int)op) || N < 0 || C < 0 || H < 0 || W < 0) return SWS_ERR_INVALID_ARG;
     if (dtype != SWS_DTYPE_BF16 && dtype != SWS_DTYPE_F16) return SWS_ERR_INVALID_ARG;
@@ -203,13 +210,13 @@ sws_status sws_pool2d_16(sws_op op, sws_dtype dtype, const void *x, void *y, int
     if (H * W > kMaxDim) return SWS_ERR_UNSUPPORTED;
     if (planes == 0) return SWS_OK;
     if (!x || !y) return SWS_ERR_INVALID_ARG;
-    return from_hip(sws::launch_pool2d_16((int)op, (int)dtype, x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale,
+    return SWS_LAUNCH(sws::launch_pool2d_16((int)op, (int)dtype, x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, scale,
                                           (hipStream_t)stream));
 }
 
 sws_status sws_pool2d_ex(sws_op op, const float *x, float *y, int64_t N, int64_t C, int64_t H, int64_t W,
                          int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t pad_top, int32_t pad_left,
-                         int32_t pad_bottom, int32_t pad_right, sws_divisor divisor, float scale, void *stream)
+                         int32_t pad_bottom, int32_t pad_right, sws_divisor divisor, float scale, sws_stream_t stream)
 {
     if (!valid_op((int)op) || N < 0 || C < 0 || H < 1 || W < 1) return SWS_ERR_INVALID_ARG;
     if (kh < 1 || kw < 1 || sh < 1 || sw < 1) return SWS_ERR_INVALID_ARG;
@@ -226,13 +233,13 @@ sws_status sws_pool2d_ex(sws_op op, const float *x, float *y, int64_t N, int64_t
     if (H * W > kMaxDim) return SWS_ERR_UNSUPPORTED;
     if (planes == 0) return SWS_OK;
     if (!x || !y) return SWS_ERR_INVALID_ARG;
-    return from_hip(sws::launch_pool2d((int)op, x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, pad_top, pad_left, scale,
+    return SWS_LAUNCH(sws::launch_pool2d((int)op, x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, pad_top, pad_left, scale,
                                        divisor == SWS_DIV_REAL_CELLS ? 1 : 0, (hipStream_t)stream));
 }
 
 sws_status sws_conv1d(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin, int64_t L,
                       int64_t Cout, int32_t k, int32_t stride, int32_t pad, int32_t dilation,
-                      int32_t groups, void *stream)
+                      int32_t groups, sws_stream_t stream)
 {
     if (B < 0 || Cin < 1 || L < 0 || Cout < 1 || k < 1 || stride < 1 || pad < 0 || dilation < 1 || groups < 1)
         return SWS_ERR_INVALID_ARG;
@@ -245,13 +252,13 @@ sws_status sws_conv1d(const float *x, const float *wgt, float *y, int64_t B, int
         return SWS_ERR_INVALID_ARG;
     if (B == 0) return SWS_OK;
     if (!x || !wgt || !y) return SWS_ERR_INVALID_ARG;
-    return from_hip(sws::launch_conv1d(x, wgt, y, B, Cin, L, Cout, Lo, k, stride, pad, dilation, groups,
+    return SWS_LAUNCH(sws::launch_conv1d(x, wgt, y, B, Cin, L, Cout, Lo, k, stride, pad, dilation, groups,
                                        (hipStream_t)stream));
 }
 
 sws_status sws_conv1d_16(sws_dtype dtype, const void *x, const float *wgt, void *y, int64_t B, int64_t Cin, int64_t L,
                          int64_t Cout, int32_t k, int32_t stride, int32_t pad, int32_t dilation, int32_t groups,
-                         void *stream)
+                         sws_stream_t stream)
 {
     if (dtype != SWS_DTYPE_BF16 && dtype != SWS_DTYPE_F16) return SWS_ERR_INVALID_ARG;
     if (B < 0 || Cin < 1 || L < 0 || Cout < 1 || k < 1 || stride < 1 || pad < 0 || dilation < 1 || groups < 1)
@@ -265,7 +272,7 @@ sws_status sws_conv1d_16(sws_dtype dtype, const void *x, const float *wgt, void 
         return SWS_ERR_INVALID_ARG;
     if (B == 0) return SWS_OK;
     if (!x || !wgt || !y) return SWS_ERR_INVALID_ARG;
-    return from_hip(sws::launch_conv1d_16((int)dtype, x, wgt, y, B, Cin, L, Cout, Lo, k, stride, pad, dilation, groups,
+    return SWS_LAUNCH(sws::launch_conv1d_16((int)dtype, x, wgt, y, B, Cin, L, Cout, Lo, k, stride, pad, dilation, groups,
                                           (hipStream_t)stream));
 }
 
@@ -291,26 +298,26 @@ sws_status check_conv1d(int64_t B, int64_t Cin, int64_t L, int64_t Cout, int32_t
 
 sws_status sws_conv1d_grad_input(const float *gy, const float *wgt, float *gx, int64_t B, int64_t Cin, int64_t L,
                                  int64_t Cout, int32_t k, int32_t stride, int32_t pad, int32_t dilation,
-                                 int32_t groups, void *stream)
+                                 int32_t groups, sws_stream_t stream)
 {
     int64_t Lo;
     const sws_status st = check_conv1d(B, Cin, L, Cout, k, stride, pad, dilation, groups, &Lo);
     if (st != SWS_OK) return st;
     if (B == 0) return SWS_OK;
     if (!gy || !wgt || !gx) return SWS_ERR_INVALID_ARG;
-    return from_hip(sws::launch_conv1d_grad_input(gy, wgt, gx, B, Cin, L, Cout, Lo, k, stride, pad, dilation, groups,
+    return SWS_LAUNCH(sws::launch_conv1d_grad_input(gy, wgt, gx, B, Cin, L, Cout, Lo, k, stride, pad, dilation, groups,
                                                   (hipStream_t)stream));
 }
 
 sws_status sws_conv1d_grad_weight(const float *x, const float *gy, float *gw, int64_t B, int64_t Cin, int64_t L,
                                   int64_t Cout, int32_t k, int32_t stride, int32_t pad, int32_t dilation,
-                                  int32_t groups, void *stream)
+                                  int32_t groups, sws_stream_t stream)
 {
     int64_t Lo;
     const sws_status st = check_conv1d(B, Cin, L, Cout, k, stride, pad, dilation, groups, &Lo);
     if (st != SWS_OK) return st;
     if (!gw || (B > 0 && (!x || !gy))) return SWS_ERR_INVALID_ARG;      // with no images gw is all zeros
-    return from_hip(sws::launch_conv1d_grad_weight(x, gy, gw, B, Cin, L, Cout, Lo, k, stride, pad, dilation, groups,
+    return SWS_LAUNCH(sws::launch_conv1d_grad_weight(x, gy, gw, B, Cin, L, Cout, Lo, k, stride, pad, dilation, groups,
                                                    (hipStream_t)stream));
 }
 
@@ -337,32 +344,32 @@ sws_status check_conv2d(int64_t N, int64_t Cin, int64_t H, int64_t W, int64_t Co
 
 sws_status sws_conv2d_grad_input(const float *gy, const float *wgt, float *gx, int64_t N, int64_t Cin, int64_t H,
                                  int64_t W, int64_t Cout, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph,
-                                 int32_t pw, void *stream)
+                                 int32_t pw, sws_stream_t stream)
 {
     int64_t Ho, Wo;
     const sws_status st = check_conv2d(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, &Ho, &Wo);
     if (st != SWS_OK) return st;
     if (N == 0) return SWS_OK;
     if (!gy || !wgt || !gx) return SWS_ERR_INVALID_ARG;
-    return from_hip(sws::launch_conv2d_grad_input(gy, wgt, gx, N, Cin, H, W, Cout, Ho, Wo, kh, kw, sh, sw, ph, pw,
+    return SWS_LAUNCH(sws::launch_conv2d_grad_input(gy, wgt, gx, N, Cin, H, W, Cout, Ho, Wo, kh, kw, sh, sw, ph, pw,
                                                   (hipStream_t)stream));
 }
 
 sws_status sws_conv2d_grad_weight(const float *x, const float *gy, float *gw, int64_t N, int64_t Cin, int64_t H,
                                   int64_t W, int64_t Cout, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph,
-                                  int32_t pw, void *stream)
+                                  int32_t pw, sws_stream_t stream)
 {
     int64_t Ho, Wo;
     const sws_status st = check_conv2d(N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw, &Ho, &Wo);
     if (st != SWS_OK) return st;
     if (!gw || (N > 0 && (!x || !gy))) return SWS_ERR_INVALID_ARG;      // with no images gw is all zeros
-    return from_hip(sws::launch_conv2d_grad_weight(x, gy, gw, N, Cin, H, W, Cout, Ho, Wo, kh, kw, sh, sw, ph, pw,
+    return SWS_LAUNCH(sws::launch_conv2d_grad_weight(x, gy, gw, N, Cin, H, W, Cout, Ho, Wo, kh, kw, sh, sw, ph, pw,
                                                    (hipStream_t)stream));
 }
 
 sws_status sws_conv2d(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
                       int64_t W, int64_t Cout, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph,
-                      int32_t pw, void *stream)
+                      int32_t pw, sws_stream_t stream)
 {
     if (N < 0 || Cin < 1 || H < 0 || W < 0 || Cout < 1) return SWS_ERR_INVALID_ARG;
     if (kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0) return SWS_ERR_INVALID_ARG;
@@ -376,7 +383,7 @@ sws_status sws_conv2d(const float *x, const float *wgt, float *y, int64_t N, int
     if (H * W > kMaxDim || Ho * Wo > kMaxDim || n_w > kMaxDim) return SWS_ERR_UNSUPPORTED;
     if (N == 0) return SWS_OK;
     if (!x || !wgt || !y) return SWS_ERR_INVALID_ARG;
-    return from_hip(sws::launch_conv2d(x, wgt, y, N, Cin, H, W, Cout, Ho, Wo, kh, kw, sh, sw, ph, pw,
+    return SWS_LAUNCH(sws::launch_conv2d(x, wgt, y, N, Cin, H, W, Cout, Ho, Wo, kh, kw, sh, sw, ph, pw,
                                        (hipStream_t)stream));
 }
 

@@ -3,21 +3,34 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "sws.h"
+#include "sws_dev.h"
 
 namespace sws {
 
-// Developer knobs set through sws_set_option(); 0 means "choose automatically".
+// Measurement knobs set through sws_set_option(); 0 means "choose automatically".  Host-side only;
+// every launcher reads a knob once (relaxed atomic load through Knob's conversion).
+struct Knob {
+    std::atomic<int> v{0};
+    operator int() const { return v.load(std::memory_order_relaxed); }
+    Knob &operator=(int x) { v.store(x, std::memory_order_relaxed); return *this; }
+};
 struct Options {
-    int slide_variant;
-    int slide_chunk;
-    int slide_group;
-    int pool2d_variant;
-    int conv1d_variant;
-    int conv2d_variant;
-    int copy_variant;
+    Knob slide_variant;
+    Knob slide_chunk;
+    Knob slide_group;
+    Knob pool2d_variant;
+    Knob conv1d_variant;
+    Knob conv2d_variant;
+    Knob copy_variant;
 };
 extern Options g_opt;
+
+// A launcher's answer when its kernel does not cover the request (the caller then tries the next
+// kernel); never a code the HIP runtime returns.
+constexpr hipError_t kNotTaken = (hipError_t)2047;
 
 constexpr int kWave = 64;    // CDNA wavefront width
 constexpr int kXcd = 8;      // XCDs (separate L2s) on MI355X

@@ -7,7 +7,7 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "sws.h")
+HEADERS = [os.path.join(ROOT, "include", n) for n in ("sws.h", "sws_dev.h")]
 
 
 @pytest.fixture(scope="module")
@@ -20,9 +20,11 @@ def L():
 
 
 def _declared():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(sws_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for h in HEADERS:
+        text = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names |= set(re.findall(r"\b(sws_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_symbols_are_exported(L):
@@ -213,3 +215,17 @@ def test_conv1d_16_argument_checks(L):
     assert c(groups=3) == 1 and c(k=0) == 1 and c(k=33) == 1 and c(stride=0) == 1 and c(dil=0) == 1 and c(pad=-1) == 1
     assert c(x=nul) == 1 and c(w=nul) == 1 and c(y=nul) == 1
     assert c(L=2 ** 31) == 1
+
+
+def test_headers_compile_as_plain_c(tmp_path):
+    """The boundary is a C ABI: both headers must be valid C99 with no HIP include."""
+    import shutil
+    import subprocess
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use.c"
+    src.write_text('#include "sws.h"\n#include "sws_dev.h"\n'
+                   'int f(sws_stream_t s) { return (int)sws_slide1d(SWS_OP_ADD, 0, 0, 0, 8, 3, 1.0f, s); }\n')
+    subprocess.run([cc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-fsyntax-only",
+                    "-I", os.path.join(ROOT, "include"), str(src)], check=True)
