@@ -45,6 +45,8 @@ def parse_args():
                     help="profiling aid: launch just this operator --steps times and print nothing but a "
                          "short note (names: the keys of 'kernels' and 'ops', or 'copy' for the 2 GiB "
                          "calibration copy)")
+    ap.add_argument("--opt", action="append", default=[], metavar="KEY=VALUE",
+                    help="with --only: set a measurement knob of sws_dev.h first (A/B profiles), e.g. conv2d_variant=2")
     return ap.parse_args()
 
 
@@ -644,6 +646,9 @@ def main():
         sys.exit(2)
     B.lib()                                       # fail loudly if the HIP library is missing
     if args.only:
+        for kv in args.opt:
+            key, _, val = kv.partition("=")
+            B.sws_set_option(key, int(val))
         run_only(torch, B, workloads, args.only, args.steps, args.cold)
         return
 

@@ -437,20 +437,6 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
     finish(buf ^ 1);
 }
 
-int device_cus()
-{
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-            cus = v;
-        else
-            return 256;
-    }
-    return cus;
-}
-
 template <int CIN, int KH, int KW, bool MODE_B, int CGS, bool WADJ>
 hipError_t launch_stream1(const float *x, const float *wgt, float *y, const StreamGeom &g, size_t lds, int grid,
                          hipStream_t s)
@@ -538,10 +524,12 @@ hipError_t launch_conv2d_stream(const float *x, const float *wgt, float *y, int6
     g.inv_Wo = 1.0f / (float)g.Wo;
     g.T = (long long)g.co_tiles * N * g.BPI;
     const int cus = device_cus();
-    // line numbers inside a run stay below 2^20 (the reciprocal division), and a run should be a few blocks
-    // long for the weights and the first lines to pay off
+    // line numbers inside a run stay below 2^20 (the reciprocal division), and a run must be long enough
+    // for the weights and the first lines to pay off: about 13000 cycles of set-up against 1024 cycles of
+    // matrix work per block and tap.  Measured: [16,64,4096] x [64,64,3] (24 block-taps per CU) 25.2 us here
+    // against 21.6 us on the tile kernel; [32,64,56,56] x [64,64,3,3] (110 per CU) 75 - 83 us against 83 - 85 us.
     const int64_t lines_per_run = (g.T / cus + 2) / g.BPI * g.LPI + 2LL * g.LPI;
-    if ((g.T < 4LL * cus && g_opt.conv2d_variant != 17) || lines_per_run >= (1 << 20)) return hipSuccess;
+    if ((g.T * kh * kw < 60LL * cus && g_opt.conv2d_variant != 17) || lines_per_run >= (1 << 20)) return hipSuccess;
     *taken = true;
     if (mode_b) return launch_stream<64, 1, 3, true, 1>(x, wgt, y, g, lds, cus, s);
     if (cgs == 0) return launch_stream<64, 3, 3, false, 0>(x, wgt, y, g, lds, cus, s);

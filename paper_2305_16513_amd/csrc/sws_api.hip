@@ -5,6 +5,20 @@
 
 namespace sws {
 Options g_opt;
+
+int device_cus()
+{
+    static std::atomic<int> cus{0};
+    int v = cus.load(std::memory_order_relaxed);
+    if (v == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+            return 256;
+        cus.store(v, std::memory_order_relaxed);
+    }
+    return v;
+}
 }
 
 namespace {

@@ -90,6 +90,9 @@ inline int max_origin_shift(int64_t lo, int line)
     return line - b;
 }
 
+// Compute units of the current device (256 on MI355X), asked once.
+int device_cus();
+
 inline int64_t xcd_grid(int64_t n_units) { return ((n_units + kXcd - 1) / kXcd) * kXcd; }
 
 hipError_t launch_copy(const float *src, float *dst, int64_t n, hipStream_t s);

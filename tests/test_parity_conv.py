@@ -363,19 +363,20 @@ def test_streaming_kernel_1d(B, geom):
 
 
 def test_streaming_kernel_against_tile_kernel_full_size(B):
-    """cfg 4 on both matrix-core kernels (option 16 switches the streaming one off): both within tolerance of
-    the oracle, and of each other."""
+    """cfg 4 on all three matrix-core kernels (option 2 switches the streaming one off and leaves the tile
+    kernel with 128-bit operand reads; 16 also switches that one off, leaving the scalar-read kernel): each
+    within tolerance of the oracle."""
     x, w = workloads.make(4)
     ref, mag = oracle.conv2d(x, w, 1, 1, 1, 1)
     xg, wg = to_gpu(x), to_gpu(w)
-    ys = to_host(B.sws_conv2d(xg, wg, 1, 1, 1, 1))
-    B.sws_set_option("conv2d_variant", 16)
-    try:
-        yt = to_host(B.sws_conv2d(xg, wg, 1, 1, 1, 1))
-    finally:
-        B.sws_set_option("conv2d_variant", 0)
-    assert_within_tol(ys, ref, mag, "cfg4 streaming kernel")
-    assert_within_tol(yt, ref, mag, "cfg4 tile kernel")
+    assert_within_tol(to_host(B.sws_conv2d(xg, wg, 1, 1, 1, 1)), ref, mag, "cfg4 streaming kernel")
+    for variant, name in ((2, "tile kernel"), (16, "scalar-read kernel")):
+        B.sws_set_option("conv2d_variant", variant)
+        try:
+            yt = to_host(B.sws_conv2d(xg, wg, 1, 1, 1, 1))
+        finally:
+            B.sws_set_option("conv2d_variant", 0)
+        assert_within_tol(yt, ref, mag, "cfg4 " + name)
 
 
 def test_cfg1_correlation_full_size(B):
