@@ -419,6 +419,13 @@ hipError_t launch_maxpool2d_grad(const float *x, const float *gy, float *gx, int
                                  int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph,
                                  int32_t pw, hipStream_t s)
 {
+    // 3 x 3 windows on rows that fit a wavefront: the row-streaming kernel (pool2d_variant bit 128 switches it off)
+    if (g_opt.pool2d_variant != 1 && !(g_opt.pool2d_variant & 128)) {
+        bool taken = false;
+        const hipError_t e = launch_maxpool2d_grad_rows(x, gy, gx, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw,
+                                                        ph, pw, s, &taken);
+        if (taken) return e;
+    }
     PgGeom g;
     g.H = (int)H; g.W = (int)W; g.Ho = (int)Ho; g.Wo = (int)Wo; g.kh = kh; g.kw = kw; g.sh = sh; g.sw = sw; g.ph = ph; g.pw = pw;
     g.pwl = pw;
@@ -485,6 +492,16 @@ hipError_t launch_avgpool2d_grad(const float *gy, float *gx, int64_t planes, int
                                  int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw, int div_real,
                                  float scale, hipStream_t s)
 {
+    if (!div_real && g_opt.pool2d_variant != 1 && !(g_opt.pool2d_variant & 128)) {
+        // At stride 1 with one divisor the adjoint IS the forward sliding sum, over gy padded by k - 1 - p
+        // (a cell's windows are the k x k block of gy around it): the forward kernels take it.
+        if (sh == 1 && sw == 1)
+            return launch_pool2d(SWS_OP_ADD, gy, gx, planes, Ho, Wo, H, W, kh, kw, 1, 1, kh - 1 - ph, kw - 1 - pw, scale, 0, s);
+        bool taken = false;
+        const hipError_t e = launch_avgpool2d_grad_rows(gy, gx, planes, (int)H, (int)W, (int)Ho, (int)Wo, kh, kw, sh, sw, ph,
+                                                        pw, scale, s, &taken);
+        if (taken) return e;
+    }
     PgGeom g;
     g.H = (int)H; g.W = (int)W; g.Ho = (int)Ho; g.Wo = (int)Wo; g.kh = kh; g.kw = kw; g.sh = sh; g.sw = sw; g.ph = ph; g.pw = pw;
     g.pwl = pw; g.PX = 0; g.x_rows = 0; g.cwx = g.kmx = g.cwg = g.kmg = 0;

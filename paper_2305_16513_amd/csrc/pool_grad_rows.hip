@@ -1,0 +1,333 @@
+// Adjoints of 3 x 3 pooling (one column of padding, stride 1 or 2) on planes whose rows fit a
+// wavefront — the backward passes of the row-streaming pooling kernel (Section 2.3 used for
+// training), without LDS.  W a multiple of 4, 4 <= W <= 256; stride 1: Wo = W, stride 2: Wo = W / 2.
+//
+// As in the forward kernel a lane owns four adjacent columns, the W/4 lanes of a group move a row as
+// one contiguous run of 128-bit accesses, the G = 64 / (W/4) groups of a wavefront take G consecutive
+// bands of TH rows of gx, a wavefront is a workgroup of its own, and XCD b mod 8 takes the planes
+// 8q + (b mod 8) band by band.  What a lane needs from beside its columns comes from the neighbouring
+// lanes by DPP shifts.
+//
+// Max pooling: every window's gradient goes to the first cell (row-major) that holds its maximum.
+// A band's lane keeps the x rows its windows see; per row it forms, for each of its window columns,
+// the maximum of the three cells and WHICH cell it was, as the number 8 * (row of the band) + (column
+// among the lane's six, its neighbours' included) — strict comparisons, so the first of equal cells
+// wins; three rows combine the same way down H.  A window thus ends up with the number of the one
+// cell that receives its gradient, and a cell adds the gradients of the windows whose number is its
+// own — no window-relative arithmetic, no range tests: a window that does not contain a cell cannot
+// carry its number.  Windows outside the plane are given gradient 0; cells outside the plane hold -inf.
+//
+// Average pooling at stride 2: the same bands with sums instead of numbers (at stride 1 the adjoint is
+// the forward sliding sum over gy and runs on the forward kernels).
+#include "sws_internal.h"
+
+namespace sws {
+
+namespace {
+
+typedef v2f v2f_u __attribute__((aligned(4)));
+
+__device__ __forceinline__ float lane_before(float v)       // the value held by lane - 1
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x138, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float lane_after(float v)        // the value held by lane + 1
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x130, 0xf, 0xf, false));
+}
+__device__ __forceinline__ int lane_before(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x138, 0xf, 0xf, false); }
+__device__ __forceinline__ int lane_after(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x130, 0xf, 0xf, false); }
+
+// Where a wavefront's lane works: group (band) and lane within the row; false = nothing to do.
+struct Where {
+    int l;                  // lane within its row: columns 4l .. 4l + 3
+    int r0;                 // first gx row of the band
+    int64_t plane;
+    bool first, last;       // the row's edge lanes
+};
+__device__ __forceinline__ bool locate(Where &w, int LPR, int G, int lpr_rcp, int TH, int H, int64_t planes)
+{
+    const int lane = threadIdx.x;
+    const int grp = (lane * lpr_rcp) >> 16;                          // lane / LPR (exact for lane < 64)
+    w.l = lane - grp * LPR;
+    if (grp >= G) return false;
+    w.plane = (int64_t)blockIdx.y * kXcd + (blockIdx.x & 7);        // gridDim.x is a multiple of 8: XCD = x & 7
+    if (w.plane >= planes) return false;
+    w.r0 = ((int)(blockIdx.x >> 3) * G + grp) * TH;
+    if (w.r0 >= H) return false;
+    w.first = w.l == 0;
+    w.last = w.l == LPR - 1;
+    return true;
+}
+
+// One x row -> for each of the lane's NW window columns the maximum of its three cells (hm) and the
+// number of the first cell holding it (hc), numbers being base + (column among e[0..5]).
+// STEP = 1: windows u = 0..3 see e[u .. u+2]; STEP = 2: windows u = 0, 1 see e[2u .. 2u+2].
+template <int STEP, int NW>
+__device__ __forceinline__ void row_maxima(const float (&e)[6], int base, float (&hm)[NW], int (&hc)[NW])
+{
+#pragma unroll
+    for (int u = 0; u < NW; ++u) {
+        const int c = STEP * u;
+        float m = e[c];
+        int k = base + c;
+        if (e[c + 1] > m) { m = e[c + 1]; k = base + c + 1; }
+        if (e[c + 2] > m) { m = e[c + 2]; k = base + c + 2; }
+        hm[u] = m;
+        hc[u] = k;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Max pooling, stride S.  gx rows r0 .. r0 + TH - 1 of a plane; TH even for S = 2.
+//   S = 1: window row ho covers x rows ho - ph .. + 2; the band's windows are ho = r0 + ph - 2 + i,
+//          i < TH + 2, over x rows r0 - 2 + j, j < TH + 4: window i = rows j = i, i+1, i+2; cell row t
+//          is j = t + 2 and lies in windows t, t+1, t+2.
+//   S = 2: window row ho covers x rows 2 ho - ph .. + 2; windows ho = hf + i, hf = ceil((r0 + ph - 2) / 2),
+//          i < TH/2 + 1, over x rows 2 hf - ph + j, j < TH + 3: window i = rows 2i, 2i+1, 2i+2; cell row t
+//          is j = d0 + t with d0 = r0 + ph - 2 hf (1 or 2).
+// Columns.  S = 1: window wo covers columns wo - 1 .. wo + 1; the lane's windows are wo = 4l + u, u < 4,
+//          over e[0..5] = columns 4l - 1 .. 4l + 4; cell v (column 4l + v, e[v + 1]) lies in windows
+//          v - 1, v, v + 1, of which u = -1 is the previous lane's u = 3 (where the cell is e[5]) and
+//          u = 4 the next lane's u = 0 (where it is e[0]).
+//          S = 2: window wo covers columns 2 wo - 1 .. 2 wo + 1; the lane's windows are wo = 2l + u, u < 2,
+//          over e[0..4]; cell 0 lies in window 0, cell 1 in 0 and 1, cell 2 in 1, cell 3 in 1 and in the
+//          next lane's window 0 (where it is e[0]).
+// ------------------------------------------------------------------------------------------------
+template <int S, int TH>
+__global__ __launch_bounds__(kWave) void maxpool_grad_rows_kernel(const float *__restrict__ x, const float *__restrict__ gy,
+                                                                  float *__restrict__ gx, int H, int W, int Ho, int Wo,
+                                                                  int ph, int LPR, int G, int lpr_rcp, int64_t planes)
+{
+    static_assert(S == 1 || (S == 2 && TH % 2 == 0), "bands of an even number of rows at stride 2");
+    constexpr int NW = S == 1 ? 4 : 2;                               // window columns of a lane
+    constexpr int NWR = S == 1 ? TH + 2 : TH / 2 + 1;                // window rows of a band
+    constexpr int NXR = S == 1 ? TH + 4 : TH + 3;                    // x rows of a band
+    const float ninf = -__builtin_huge_valf();
+    Where w;
+    if (!locate(w, LPR, G, lpr_rcp, TH, H, planes)) return;
+    const int hf = S == 1 ? w.r0 + ph - 2 : (w.r0 + ph - 1) >> 1;    // first window row (may be < 0)
+    const int xr0 = S == 1 ? w.r0 - 2 : 2 * hf - ph;                 // first x row (may be < 0)
+    const int d0 = S == 1 ? 2 : w.r0 - xr0;                          // cell row t is x row j = d0 + t
+    const float *xp = x + w.plane * (int64_t)H * W + 4 * w.l;
+    const float *gp = gy + w.plane * (int64_t)Ho * Wo + NW * w.l;
+    float *op = gx + w.plane * (int64_t)H * W + 4 * w.l;
+
+    // ---- all loads in flight together; rows outside the plane: -inf cells, zero gradients
+    v4f xr[NXR];
+#pragma unroll
+    for (int j = 0; j < NXR; ++j) {
+        const int row = xr0 + j;
+        const bool ok = row >= 0 && row < H;
+        const v4f v = *(const v4f_u *)(xp + (int64_t)(ok ? row : 0) * W);
+        xr[j] = ok ? v : (v4f){ninf, ninf, ninf, ninf};
+    }
+    float g[NWR][NW];
+#pragma unroll
+    for (int i = 0; i < NWR; ++i) {
+        const int ho = hf + i;
+        const bool ok = ho >= 0 && ho < Ho;
+        const float *src = gp + (int64_t)(ok ? ho : 0) * Wo;
+        if constexpr (NW == 4) {
+            const v4f v = *(const v4f_u *)src;
+            g[i][0] = ok ? v.x : 0.0f; g[i][1] = ok ? v.y : 0.0f; g[i][2] = ok ? v.z : 0.0f; g[i][3] = ok ? v.w : 0.0f;
+        } else {
+            const v2f v = *(const v2f_u *)src;
+            g[i][0] = ok ? v.x : 0.0f; g[i][1] = ok ? v.y : 0.0f;
+        }
+    }
+
+    // ---- per x row: maxima along W with the number of the cell that holds them, folded at once into the
+    //      (up to three) windows the row belongs to: down H the first row wins ties.  wn = number of the
+    //      cell that receives the window's gradient.
+    float wm[NWR][NW];
+    int wn[NWR][NW];
+#pragma unroll
+    for (int j = 0; j < NXR; ++j) {
+        float e[6];
+        e[1] = xr[j].x; e[2] = xr[j].y; e[3] = xr[j].z; e[4] = xr[j].w;
+        const float b = lane_before(xr[j].w);
+        e[0] = w.first ? ninf : b;
+        if constexpr (S == 1) {
+            const float a = lane_after(xr[j].x);
+            e[5] = w.last ? ninf : a;
+        } else {
+            e[5] = ninf;                                             // (not read)
+        }
+        float hm[NW];
+        int hc[NW];
+        row_maxima<S, NW>(e, 8 * j, hm, hc);
+#pragma unroll
+        for (int i = 0; i < NWR; ++i) {
+            const int a = j - S * i;                                 // the row's place in window i
+            if (a < 0 || a > 2) continue;
+#pragma unroll
+            for (int u = 0; u < NW; ++u) {
+                if (a == 0) {
+                    wm[i][u] = hm[u];
+                    wn[i][u] = hc[u];
+                } else {
+                    const bool better = hm[u] > wm[i][u];
+                    wm[i][u] = better ? hm[u] : wm[i][u];
+                    wn[i][u] = better ? hc[u] : wn[i][u];
+                }
+            }
+        }
+    }
+    // ---- the windows beside the lane's: the previous lane's last (S = 1 only) and the next lane's first
+    int wn_b[NWR], wn_a[NWR];
+    float g_b[NWR], g_a[NWR];
+#pragma unroll
+    for (int i = 0; i < NWR; ++i) {
+        if constexpr (S == 1) {
+            wn_b[i] = lane_before(wn[i][NW - 1]);
+            const float t = lane_before(g[i][NW - 1]);
+            g_b[i] = w.first ? 0.0f : t;
+        } else {
+            wn_b[i] = 0;
+            g_b[i] = 0.0f;
+        }
+        wn_a[i] = lane_after(wn[i][0]);
+        const float t = lane_after(g[i][0]);
+        g_a[i] = w.last ? 0.0f : t;
+    }
+    // ---- every cell adds the gradients of the windows that carry its number
+#pragma unroll
+    for (int t = 0; t < TH; ++t) {
+        const int row = w.r0 + t;
+        float o[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int me = 8 * (d0 + t) + v + 1;                     // my number in this lane's numbering
+            float acc = 0.0f;
+            if constexpr (S == 1) {
+#pragma unroll
+                for (int di = 0; di < 3; ++di) {
+                    const int i = t + di;
+#pragma unroll
+                    for (int du = 0; du < 3; ++du) {
+                        const int u = v - 1 + du;
+                        if (u < 0) acc += (wn_b[i] == 8 * (d0 + t) + 5) ? g_b[i] : 0.0f;
+                        else if (u > 3) acc += (wn_a[i] == 8 * (d0 + t) + 0) ? g_a[i] : 0.0f;
+                        else acc += (wn[i][u] == me) ? g[i][u] : 0.0f;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < NWR; ++i) {
+                    if (v <= 1) acc += (wn[i][0] == me) ? g[i][0] : 0.0f;
+                    if (v >= 1) acc += (wn[i][1] == me) ? g[i][1] : 0.0f;
+                    if (v == 3) acc += (wn_a[i] == 8 * (d0 + t) + 0) ? g_a[i] : 0.0f;
+                }
+            }
+            o[v] = acc;
+        }
+        if (row < H) __builtin_nontemporal_store((v4f){o[0], o[1], o[2], o[3]}, (v4f_u *)(op + (int64_t)row * W));
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Average pooling, stride 2 (same bands): a cell adds f * gy over the windows that contain it.
+// ------------------------------------------------------------------------------------------------
+template <int TH>
+__global__ __launch_bounds__(kWave) void avgpool_grad_rows_s2_kernel(const float *__restrict__ gy, float *__restrict__ gx,
+                                                                     int H, int W, int Ho, int Wo, int ph, int LPR, int G,
+                                                                     int lpr_rcp, int64_t planes, float scale)
+{
+    static_assert(TH % 2 == 0, "bands of an even number of rows");
+    constexpr int NWR = TH / 2 + 1;
+    Where w;
+    if (!locate(w, LPR, G, lpr_rcp, TH, H, planes)) return;
+    const int hf = (w.r0 + ph - 1) >> 1;
+    const int d0 = w.r0 - (2 * hf - ph);                             // 1 or 2
+    const float *gp = gy + w.plane * (int64_t)Ho * Wo + 2 * w.l;
+    float *op = gx + w.plane * (int64_t)H * W + 4 * w.l;
+    // per window row: the sums along W that the lane's four cells receive
+    float c[NWR][4];
+#pragma unroll
+    for (int i = 0; i < NWR; ++i) {
+        const int ho = hf + i;
+        const bool ok = ho >= 0 && ho < Ho;
+        const v2f v = *(const v2f_u *)(gp + (int64_t)(ok ? ho : 0) * Wo);
+        const float g0 = ok ? v.x * scale : 0.0f, g1 = ok ? v.y * scale : 0.0f;
+        const float t = lane_after(g0);
+        const float ga = w.last ? 0.0f : t;
+        c[i][0] = g0; c[i][1] = g0 + g1; c[i][2] = g1; c[i][3] = g1 + ga;
+    }
+#pragma unroll
+    for (int t = 0; t < TH; ++t) {
+        const int row = w.r0 + t;
+        const int j = d0 + t;                                        // x row among the band's: windows i with 2i <= j <= 2i + 2
+        float o[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int i = 0; i < NWR; ++i) acc += (2 * i <= j && j <= 2 * i + 2) ? c[i][v] : 0.0f;
+            o[v] = acc;
+        }
+        if (row < H) __builtin_nontemporal_store((v4f){o[0], o[1], o[2], o[3]}, (v4f_u *)(op + (int64_t)row * W));
+    }
+}
+
+struct RowsGrid {
+    int LPR, G, rcp;
+    dim3 grid;
+    bool ok;
+};
+RowsGrid rows_grid(int64_t planes, int H, int W, int TH)
+{
+    RowsGrid r;
+    r.LPR = W / 4;
+    r.G = kWave / r.LPR;
+    r.rcp = (65536 + r.LPR - 1) / r.LPR;
+    const int bands = (H + TH - 1) / TH;
+    const int spp = (bands + r.G - 1) / r.G;                         // wavefronts per plane
+    const int64_t rounds = (planes + kXcd - 1) / kXcd;
+    r.ok = rounds <= 65535;
+    r.grid = dim3((unsigned)(spp * kXcd), (unsigned)rounds);
+    return r;
+}
+
+bool rows_shape(int H, int W, int Ho, int Wo, int kh, int kw, int sh, int sw, int ph, int pw)
+{
+    if (kh != 3 || kw != 3 || sh != sw || (sh != 1 && sh != 2) || pw != 1 || ph < 0 || ph > 2) return false;
+    if ((W & 3) || W < 4 || W > 256 || H < 1) return false;
+    return sh == 1 ? Wo == W : Wo == W / 2;
+}
+
+}  // namespace
+
+hipError_t launch_maxpool2d_grad_rows(const float *x, const float *gy, float *gx, int64_t planes, int H, int W, int Ho,
+                                      int Wo, int kh, int kw, int sh, int sw, int ph, int pw, hipStream_t s, bool *taken)
+{
+    *taken = false;
+    if (!rows_shape(H, W, Ho, Wo, kh, kw, sh, sw, ph, pw)) return hipSuccess;
+    constexpr int TH1 = 4, TH2 = 4;
+    const RowsGrid r = rows_grid(planes, H, W, sh == 1 ? TH1 : TH2);
+    if (!r.ok) return hipSuccess;
+    *taken = true;
+    if (sh == 1)
+        hipLaunchKernelGGL((maxpool_grad_rows_kernel<1, TH1>), r.grid, dim3(kWave), 0, s, x, gy, gx, H, W, Ho, Wo, ph, r.LPR,
+                           r.G, r.rcp, planes);
+    else
+        hipLaunchKernelGGL((maxpool_grad_rows_kernel<2, TH2>), r.grid, dim3(kWave), 0, s, x, gy, gx, H, W, Ho, Wo, ph, r.LPR,
+                           r.G, r.rcp, planes);
+    return hipGetLastError();
+}
+
+hipError_t launch_avgpool2d_grad_rows(const float *gy, float *gx, int64_t planes, int H, int W, int Ho, int Wo, int kh,
+                                      int kw, int sh, int sw, int ph, int pw, float scale, hipStream_t s, bool *taken)
+{
+    *taken = false;
+    if (sh != 2 || !rows_shape(H, W, Ho, Wo, kh, kw, sh, sw, ph, pw)) return hipSuccess;
+    constexpr int TH = 4;
+    const RowsGrid r = rows_grid(planes, H, W, TH);
+    if (!r.ok) return hipSuccess;
+    *taken = true;
+    hipLaunchKernelGGL((avgpool_grad_rows_s2_kernel<TH>), r.grid, dim3(kWave), 0, s, gy, gx, H, W, Ho, Wo, ph, r.LPR, r.G,
+                       r.rcp, planes, scale);
+    return hipGetLastError();
+}
+
+}  // namespace sws

@@ -124,6 +124,11 @@ hipError_t launch_maxpool2d_grad(const float *x, const float *gy, float *gx, int
 hipError_t launch_avgpool2d_grad(const float *gy, float *gx, int64_t planes, int64_t H, int64_t W, int64_t Ho, int64_t Wo,
                                  int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw, int div_real,
                                  float scale, hipStream_t s);
+// Row-streaming adjoints of 3 x 3 pooling (pool_grad_rows.hip); *taken = false: shape not covered, nothing launched.
+hipError_t launch_maxpool2d_grad_rows(const float *x, const float *gy, float *gx, int64_t planes, int H, int W, int Ho,
+                                      int Wo, int kh, int kw, int sh, int sw, int ph, int pw, hipStream_t s, bool *taken);
+hipError_t launch_avgpool2d_grad_rows(const float *gy, float *gx, int64_t planes, int H, int W, int Ho, int Wo, int kh,
+                                      int kw, int sh, int sw, int ph, int pw, float scale, hipStream_t s, bool *taken);
 hipError_t launch_pool2d_16(int op, int dtype, const void *x, void *y, int64_t planes, int64_t H, int64_t W, int64_t Ho,
                             int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
                             float scale, hipStream_t s);

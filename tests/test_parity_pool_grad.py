@@ -153,3 +153,76 @@ def test_avgpool2d_grad_argument_checks(B):
     with pytest.raises(B.SwsError):
         B.sws_avgpool2d_grad(gy, 4, 4, 3, 3, 1, 1, 1, 1, divisor=7)
     assert B.sws_avgpool2d_grad(to_gpu(np.zeros((0, 3, 4, 4), np.float32)), 4, 4, 3, 3, 1, 1, 1, 1).shape == (0, 3, 4, 4)
+
+
+# ------------------------------------------------------------------ the row-streaming adjoints (3 x 3, rows of 4 .. 256)
+ROW_PLANES = [(1, 1, 1, 4), (1, 3, 2, 8), (2, 5, 7, 12), (1, 9, 9, 60), (3, 3, 37, 112), (1, 2, 113, 256), (1, 17, 6, 20),
+              (2, 2, 56, 56), (1, 1, 300, 16)]
+
+
+@pytest.mark.parametrize("variant", [0, 128])
+@pytest.mark.parametrize("ph", [0, 1, 2])
+@pytest.mark.parametrize("stride", [1, 2])
+@pytest.mark.parametrize("shape", ROW_PLANES)
+def test_row_streaming_maxpool_grad(B, shape, stride, ph, variant):
+    """3 x 3 windows, one column of padding, every row padding: plane counts that are not a multiple of 8,
+    heights that are not a multiple of the band, rows from one lane to a whole wavefront; random data
+    (no ties) within tolerance, and planes of few distinct values (ties everywhere) with integer
+    gradients bit for bit.  variant 128 runs the same cases on the band kernel."""
+    h, wd = shape[2], shape[3]
+    if 3 > h + 2 * ph:
+        pytest.skip("window larger than plane")
+    geom = (3, 3, stride, stride, ph, 1)
+    ho, wo = (h + 2 * ph - 3) // stride + 1, (wd + 2 - 3) // stride + 1
+    r = np.random.Generator(np.random.PCG64(h * 1000 + wd + 7 * ph + stride))
+    x = r.standard_normal(shape, dtype=np.float32)
+    gy = r.standard_normal(shape[:2] + (ho, wo), dtype=np.float32)
+    xi = workloads.integer_valued(shape, 0, 2, h + wd)
+    gi = workloads.integer_valued(shape[:2] + (ho, wo), -3, 3, h * wd)
+    B.sws_set_option("pool2d_variant", variant)
+    try:
+        _check(B, x, gy, geom, "rows max grad %s s%d ph%d" % (shape, stride, ph))
+        gx, ref = _check(B, xi, gi, geom, "rows max grad, ties %s s%d ph%d" % (shape, stride, ph))
+    finally:
+        B.sws_set_option("pool2d_variant", 0)
+    assert np.array_equal(gx.astype(np.float64), ref)
+    assert np.array_equal(gx.astype(np.float64).sum(axis=(2, 3)), gi.astype(np.float64).sum(axis=(2, 3)))
+
+
+@pytest.mark.parametrize("variant", [0, 128])
+@pytest.mark.parametrize("ph", [0, 1, 2])
+@pytest.mark.parametrize("stride", [1, 2])
+@pytest.mark.parametrize("shape", ROW_PLANES)
+def test_row_streaming_avgpool_grad(B, shape, stride, ph, variant):
+    h, wd = shape[2], shape[3]
+    if 3 > h + 2 * ph:
+        pytest.skip("window larger than plane")
+    geom = (3, 3, stride, stride, ph, 1)
+    ho, wo = (h + 2 * ph - 3) // stride + 1, (wd + 2 - 3) // stride + 1
+    r = np.random.Generator(np.random.PCG64(h * 1000 + wd + 7 * ph + stride + 1))
+    gy = r.standard_normal(shape[:2] + (ho, wo), dtype=np.float32)
+    gi = workloads.integer_valued(shape[:2] + (ho, wo), -3, 3, h * wd + 1)
+    B.sws_set_option("pool2d_variant", variant)
+    try:
+        _check_avg(B, gy, h, wd, geom, 0, 1.0 / 9, "rows avg grad %s s%d ph%d" % (shape, stride, ph))
+        gx, ref = _check_avg(B, gi, h, wd, geom, 0, 0.5, "rows avg grad, integers %s s%d ph%d" % (shape, stride, ph))
+    finally:
+        B.sws_set_option("pool2d_variant", 0)
+    assert np.array_equal(gx.astype(np.float64), ref)
+
+
+def test_row_streaming_adjoints_guard_band(B):
+    """Nothing is written outside gx."""
+    import torch
+    r = np.random.Generator(np.random.PCG64(77))
+    for stride in (1, 2):
+        x = torch.from_numpy(r.standard_normal((3, 3, 21, 36), dtype=np.float32)).cuda()
+        ho, wo = (21 + 2 - 3) // stride + 1, (36 + 2 - 3) // stride + 1
+        gy = torch.from_numpy(r.standard_normal((3, 3, ho, wo), dtype=np.float32)).cuda()
+        n = x.numel()
+        for fn in (lambda out: B.sws_maxpool2d_grad(x, gy, 3, 3, stride, stride, 1, 1, gx=out),
+                   lambda out: B.sws_avgpool2d_grad(gy, 21, 36, 3, 3, stride, stride, 1, 1, scale=1 / 9, gx=out)):
+            buf = torch.full((n + 256,), 7.0, device="cuda")
+            fn(buf[128:128 + n].view(3, 3, 21, 36))
+            torch.cuda.synchronize()
+            assert bool((buf[:128] == 7.0).all()) and bool((buf[128 + n:] == 7.0).all())
