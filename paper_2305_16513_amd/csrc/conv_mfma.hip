@@ -674,7 +674,7 @@ hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_
     }
     // the weight-stationary streaming kernel where it applies (option conv2d_variant 16 switches it off,
     // 17 takes it for small problems too)
-    if (plain && (g_opt.conv2d_variant == 0 || g_opt.conv2d_variant == 17)) {
+    if (plain && (g_opt.conv2d_variant == 0 || g_opt.conv2d_variant == 17 || g_opt.conv2d_variant == 18)) {
         const hipError_t e = launch_conv2d_stream(x, wgt, y, N, Cin, H, W, Cout, Ho, Wo, kh, kw, ph, pw, s, taken, wadj);
         if (*taken || e != hipSuccess) return e;
     }

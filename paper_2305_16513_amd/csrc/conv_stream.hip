@@ -41,11 +41,14 @@ namespace sws {
 namespace {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 512;
 constexpr int kPad = 4;                               // floats of padding per staged position
 constexpr int kScratchFloats = 2 * 2 * 4 * 3 * 64 * 4;  // [buffer][wm][owner quarter][source][lane][4]
-constexpr int kSpareFloats = 64;                      // where lanes without a column of their own write
+constexpr int kSpareFloats = 128;                     // where lanes without a column of their own write
+constexpr int kPitch3 = 384;                          // bytes per staged position, three bf16 planes of 64 channels
 
 struct StreamGeom {
     int N, H, W, Ho, Wo, ph, pw, Cout;
@@ -63,13 +66,16 @@ struct StreamGeom {
 __device__ __forceinline__ int fdiv(int x, float inv_d) { return (int)(((float)x + 0.5f) * inv_d); }
 
 // CGS = log2 of the 16-column groups per line, rounded up to a power of two (0 .. 2)
-template <int CIN, int KH, int KW, bool MODE_B, int CGS, bool WADJ>
+// X3: the arithmetic runs on the bf16 matrix cores with operands split exactly (see the file header).
+template <int CIN, int KH, int KW, bool MODE_B, int CGS, bool WADJ, bool X3 = false>
 __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__restrict__ x,
                                                                const float *__restrict__ wgt,
                                                                float *__restrict__ y, StreamGeom g)
 {
     constexpr int KT = KH * KW;
     constexpr int PITCH = CIN + kPad;
+    constexpr int PB = X3 ? kPitch3 : PITCH * 4;      // bytes per staged position
+    static_assert(!X3 || (CIN == 64 && !MODE_B && !WADJ), "the split-operand path is built for 64-channel images");
     constexpr int CQ = CIN / 4;                       // input channels per wavefront
     constexpr int NCB = CQ / 8;                       // blocks of 8 channels among them
     // staging: a group is 16 columns x 4 channels (lane = column + 16 * channel); slot s of this wavefront
@@ -80,7 +86,7 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
     constexpr int H2 = XS / 2;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     float *ring = lds;
-    float *scratch = lds + g.R * g.LW * PITCH;
+    float *scratch = lds + g.R * g.LW * (PB / 4);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -117,8 +123,12 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
     // spare area behind the scratch buffers instead — the ring is cleared once, so the zero padding
     // columns of every slot stay zero.  Rows: every lane inside the line writes (zero where the row ends).
     const bool st_wr = MODE_B ? st_in : st_colok;
-    const int st_dst = (st_pc * PITCH + st_ci) * 4;
-    char *const spare = (char *)(scratch + kScratchFloats);
+    // (X3: position st_pc, plane p, channel ci at p * 128 + 16 * ((ci >> 3) ^ (st_pc & 7)) + 2 * (ci & 7): the
+    // 16-byte groups of eight channels are permuted by the column, which spreads the 384-byte position
+    // pitch over the banks for the operand reads)
+    const int st_dst = X3 ? st_pc * PB + 2 * (st_ci & 7) : (st_pc * PITCH + st_ci) * 4;
+    const int st_key = st_pc & 7, st_c8 = st_ci >> 3;
+    char *const spare = (char *)(scratch + (X3 ? kScratchFloats / 2 : kScratchFloats));
     constexpr int SRC_STEP = 4 * CH_STEP, DST_STEP = 16 * CH_STEP;          // channels / bytes from one slot to the next
     auto line_begin = [&](int &l_n, int &l_pr, int &l_rel) {
         l_n = st_n; l_pr = st_pr; l_rel = next_line;
@@ -143,8 +153,28 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
     };
     auto commit = [&](const float (&xr)[XS], int l_pr, int l_rel, int s0, int s1) {
         const int slot = l_rel - g.R * __builtin_amdgcn_readfirstlane(fdiv(l_rel, g.inv_R));
-        char *dst = st_wr ? (char *)ring + slot * (g.LW * PITCH * 4) + st_dst : spare;
+        char *dst = st_wr ? (char *)ring + slot * (g.LW * PB) + st_dst : spare;
         const int r = MODE_B ? 0 : l_pr - g.ph;
+        if constexpr (X3) {
+            const bool real = r >= 0 && r < g.H;
+#pragma unroll
+            for (int s = 0; s < XS; ++s) {
+                if (s < s0 || s >= s1) continue;
+                if (chg0 + s * CH_STEP < CIN / 4) {
+                    // x = x1 + x2 + x3 exactly: each piece is the bf16 nearest to what the earlier ones left
+                    const float v = real ? xr[s] : 0.0f;
+                    const __bf16 v1 = (__bf16)v;
+                    const float r1 = v - (float)v1;
+                    const __bf16 v2 = (__bf16)r1;
+                    const __bf16 v3 = (__bf16)(r1 - (float)v2);
+                    char *d = dst + 16 * ((st_c8 + s * (SRC_STEP / 8)) ^ st_key);
+                    *(__bf16 *)d = v1;
+                    *(__bf16 *)(d + 128) = v2;
+                    *(__bf16 *)(d + 256) = v3;
+                }
+            }
+            return;
+        }
         if (MODE_B) {
             const bool ok = (unsigned)(st_c + 32 * l_pr) < (unsigned)g.W;
 #pragma unroll
@@ -182,7 +212,10 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
     // two halves of 32 output channels, rows padded by one float: lane = output channel then reads
     // conflict-free) and the registers are filled from there.  Uses the ring's memory: called before
     // the first line is staged, or (a later tile of output channels) re-stages the ring afterwards.
-    float w[KT][NCB][4];
+    float w[X3 ? 1 : KT][NCB][4];
+    // X3: W[co][ci = 16 wq + 8 half + e][t] as three bf16 pieces, eight channels per register quad — the A
+    // operand of v_mfma_f32_32x32x16_bf16 (lane = output channel + 32 * (k / 8), element = k % 8)
+    v8bf w3[X3 ? KT : 1][3];
     auto load_weights = [&](int tile) {
         constexpr int ROW = CIN * KT, WP = ROW + 1;
         constexpr int PER = 32 * ROW / 4 / kThreads;  // 128-bit loads per thread and half tile
@@ -219,31 +252,62 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
             }
             __syncthreads();
             if (wm == h) {
+                if constexpr (X3) {
 #pragma unroll
-                for (int cb = 0; cb < NCB; ++cb)
+                    for (int e = 0; e < 8; ++e) {
+                        const int ci = wq * CQ + 8 * half + e;
+                        const float *rd = wl + l32 * WP + ci * KT;
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int ci = wq * CQ + cb * 8 + 4 * half + j;
-                        const float *rd = WADJ ? wl + ci * (32 * KT) + l32 * KT : wl + l32 * WP + ci * KT;
-#pragma unroll
-                        for (int t = 0; t < KT; ++t) w[t][cb][j] = rd[WADJ ? KT - 1 - t : t];
+                        for (int t = 0; t < KT; ++t) {
+                            const float f = rd[t];
+                            const __bf16 f1 = (__bf16)f;
+                            const float r1 = f - (float)f1;
+                            const __bf16 f2 = (__bf16)r1;
+                            w3[t][0][e] = f1;
+                            w3[t][1][e] = f2;
+                            w3[t][2][e] = (__bf16)(r1 - (float)f2);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);            // (one channel's reads in flight at a time: registers)
                     }
+                } else {
+#pragma unroll
+                    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int ci = wq * CQ + cb * 8 + 4 * half + j;
+                            const float *rd = WADJ ? wl + ci * (32 * KT) + l32 * KT : wl + l32 * WP + ci * KT;
+#pragma unroll
+                            for (int t = 0; t < KT; ++t) w[t][cb][j] = rd[WADJ ? KT - 1 - t : t];
+                        }
+                }
             }
         }
         __syncthreads();
         // the registers are settled here, so that no matrix instruction of the loop below waits on a counter
+        if constexpr (X3) {
 #pragma unroll
-        for (int t = 0; t < KT; ++t)
+            for (int t = 0; t < KT; ++t)
 #pragma unroll
-            for (int cb = 0; cb < NCB; ++cb)
+                for (int p = 0; p < 3; ++p) {
+                    v4u q = __builtin_bit_cast(v4u, w3[t][p]);
+                    asm volatile("" : "+v"(q));
+                    w3[t][p] = __builtin_bit_cast(v8bf, q);
+                }
+        } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) asm volatile("" : "+v"(w[t][cb][j]));
+            for (int t = 0; t < KT; ++t)
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) asm volatile("" : "+v"(w[t][cb][j]));
+        }
     };
 
     // ---- where my position's taps are in the ring, for block kk of the image whose line 0 has number `base`:
     // images: one byte offset per kernel row (the taps of a row are immediates); rows: one per tap
-    constexpr int NB = MODE_B ? KW : KH;
+    constexpr int NB = X3 ? KT : (MODE_B ? KW : KH);
     const int lane_const = (wq * CQ + 4 * half) * 4;
+    const int oct = 2 * wq + half;                    // X3: my eight channels are group `oct` of a plane
     auto bases = [&](int kk, int base, int (&rb)[NB], bool &pok, int &pp) {
         const int p = 32 * kk + l32;
         pok = p < HoWo;
@@ -262,7 +326,13 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
             int slot = line - g.R * fdiv(line, g.inv_R);
 #pragma unroll
             for (int a = 0; a < KH; ++a) {
-                rb[a] = ((slot * g.LW + ow) * PITCH) * 4 + lane_const;
+                if constexpr (X3) {
+#pragma unroll
+                    for (int b = 0; b < KW; ++b)
+                        rb[a * KW + b] = (slot * g.LW + ow + b) * PB + 16 * (oct ^ ((ow + b) & 7));
+                } else {
+                    rb[a] = ((slot * g.LW + ow) * PITCH) * 4 + lane_const;
+                }
                 slot = slot + 1 == g.R ? 0 : slot + 1;
             }
         }
@@ -276,8 +346,9 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
     const v4f *sc_rd = (const v4f *)scratch + ((wm * 4 + wq) * 3) * 64 + lane;      // + buffer * 1536
     v4f *sc_wr = (v4f *)scratch + (wm * 4) * 3 * 64 + lane;
     const long long co_off = (long long)(32 * wm + 8 * wq + 4 * half) * HoWo;
+    constexpr int SCB = X3 ? 0 : 2 * 4 * 3 * 64;      // v4f per hand-over buffer (X3: one buffer, two barriers per block)
     auto finish = [&](int b) {
-        const v4f *sp = sc_rd + b * (2 * 4 * 3 * 64);
+        const v4f *sp = sc_rd + b * SCB;
         const v4f f = sp[0] + sp[64] + sp[128];
         if (pok_prev) {
 #pragma unroll
@@ -296,7 +367,7 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
     if (have_prev) { finish(buf ^ 1); have_prev = false; }
     load_weights(ct);
     if (!MODE_B) {                                    // clear the ring: its zero padding columns are never written again
-        const int n4 = g.R * g.LW * PITCH / 4;
+        const int n4 = g.R * g.LW * (PB / 16);
         for (int i = threadIdx.x; i < n4; i += kThreads) ((v4f *)ring)[i] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
         __syncthreads();
     }
@@ -348,16 +419,23 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
         v16f acc;
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-        constexpr int STEPS = KT * NCB, DEPTH = 2;
+        // (X3: a group is one operand read — piece p of the input under tap t — and the matrix instructions
+        // it feeds: the products of input piece p with weight pieces 1 .. 3 - p, i.e. every pair whose
+        // product is not below 2^-24 of the full product)
+        constexpr int STEPS = X3 ? KT * 3 : KT * NCB, DEPTH = 2;
         constexpr int I_COM = 0, I_ISS = 2, I_FIN = STEPS >= 7 ? 4 : 0, I_ADR = STEPS >= 7 ? 6 : 1, I_BAS = STEPS - 1 - DEPTH;
         static_assert(STEPS >= 4 && STEPS > DEPTH, "room for the pieces between the groups");
         v4f bq[DEPTH + 1];
         float *y_cur = y;
         int t_k3 = k3, t_n3 = n3, t_ct3 = ct3, t_base3 = base3, t_q3 = q3, t_r3 = r3, t_need3 = need3;
         auto bread = [&](int i) {
-            const int t = i / NCB, cb = i % NCB;
-            const int ofs = MODE_B ? cb * 32 : (t % KW) * PITCH * 4 + cb * 32;      // an instruction immediate
-            return *(const v4f *)((const char *)ring + rb[MODE_B ? t : t / KW] + ofs);
+            if constexpr (X3) {
+                return *(const v4f *)((const char *)ring + rb[i / 3] + (i % 3) * 128);
+            } else {
+                const int t = i / NCB, cb = i % NCB;
+                const int ofs = MODE_B ? cb * 32 : (t % KW) * PITCH * 4 + cb * 32;      // an instruction immediate
+                return *(const v4f *)((const char *)ring + rb[MODE_B ? t : t / KW] + ofs);
+            }
         };
 #pragma unroll
         for (int i = 0; i < DEPTH; ++i) bq[i] = bread(i);
@@ -366,18 +444,26 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
             if (i + DEPTH < STEPS) bq[(i + DEPTH) % (DEPTH + 1)] = bread(i + DEPTH);
             __builtin_amdgcn_sched_barrier(0);        // keep the read ahead of the MFMAs below
             const v4f b4 = bq[i % (DEPTH + 1)];
-            const int t = i / NCB, cb = i % NCB;
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w[t][cb][0], b4.x, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w[t][cb][1], b4.y, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w[t][cb][2], b4.z, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w[t][cb][3], b4.w, acc, 0, 0, 0);
+            if constexpr (X3) {
+                const v8bf b8 = __builtin_bit_cast(v8bf, b4);
+                const int t = i / 3, p = i % 3;
+#pragma unroll
+                for (int q = 2 - p; q >= 0; --q)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w3[t][q], b8, acc, 0, 0, 0);
+            } else {
+                const int t = i / NCB, cb = i % NCB;
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w[t][cb][0], b4.x, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w[t][cb][1], b4.y, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w[t][cb][2], b4.z, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w[t][cb][3], b4.w, acc, 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
             if (i == I_COM && commit_now) commit(xr0, cp, cr, 0, H2);
             if (i == I_COM + 1 && commit_now) commit(xr0, cp, cr, H2, XS);
             if (i == I_ISS && issue_now) { line_begin(n0r, p0r, r0r); issue(xr0, n0r, p0r, 0, H2); }
             if (i == I_ISS + 1 && issue_now) issue(xr0, n0r, p0r, H2, XS);
             if (i == I_FIN && have_prev) {            // the previous block: the other quarters' partial sums
-                const v4f *sp = sc_rd + (buf ^ 1) * (2 * 4 * 3 * 64);
+                const v4f *sp = sc_rd + (buf ^ 1) * SCB;
                 const v4f f = sp[0] + sp[64] + sp[128];
                 mine[0] += f.x; mine[1] += f.y; mine[2] += f.z; mine[3] += f.w;
             }
@@ -404,7 +490,8 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
         // me as its source 2 - j, so the three addresses are wave constants; which accumulator registers go
         // where depends on wq: one branch over four short copies of the code.
         {
-            v4f *wr = sc_wr + buf * (2 * 4 * 3 * 64);
+            if constexpr (X3) __syncthreads();        // one hand-over buffer: every wavefront has read the previous block's sums
+            v4f *wr = sc_wr + buf * SCB;
 #define SWS_HAND(Q0, Q1, Q2, Q3)                                                                    \
     mine[0] = acc[4 * Q0]; mine[1] = acc[4 * Q0 + 1]; mine[2] = acc[4 * Q0 + 2]; mine[3] = acc[4 * Q0 + 3];       \
     wr[(Q1 * 3 + 2) * 64] = (v4f){acc[4 * Q1], acc[4 * Q1 + 1], acc[4 * Q1 + 2], acc[4 * Q1 + 3]};                \
@@ -437,19 +524,19 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
     finish(buf ^ 1);
 }
 
-template <int CIN, int KH, int KW, bool MODE_B, int CGS, bool WADJ>
+template <int CIN, int KH, int KW, bool MODE_B, int CGS, bool WADJ, bool X3 = false>
 hipError_t launch_stream1(const float *x, const float *wgt, float *y, const StreamGeom &g, size_t lds, int grid,
                          hipStream_t s)
 {
     static bool raised = false;                       // (set once per process; the attribute is per function)
     if (!raised && lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute((const void *)conv_stream_kernel<CIN, KH, KW, MODE_B, CGS, WADJ>,
+        const hipError_t e = hipFuncSetAttribute((const void *)conv_stream_kernel<CIN, KH, KW, MODE_B, CGS, WADJ, X3>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((conv_stream_kernel<CIN, KH, KW, MODE_B, CGS, WADJ>), dim3((unsigned)grid), dim3(kThreads), lds, s, x, wgt,
-                       y, g);
+    hipLaunchKernelGGL((conv_stream_kernel<CIN, KH, KW, MODE_B, CGS, WADJ, X3>), dim3((unsigned)grid), dim3(kThreads), lds, s, x,
+                       wgt, y, g);
     return hipGetLastError();
 }
 
@@ -529,8 +616,17 @@ hipError_t launch_conv2d_stream(const float *x, const float *wgt, float *y, int6
     // matrix work per block and tap.  Measured: [16,64,4096] x [64,64,3] (24 block-taps per CU) 25.2 us here
     // against 21.6 us on the tile kernel; [32,64,56,56] x [64,64,3,3] (110 per CU) 75 - 83 us against 83 - 85 us.
     const int64_t lines_per_run = (g.T / cus + 2) / g.BPI * g.LPI + 2LL * g.LPI;
-    if ((g.T * kh * kw < 60LL * cus && g_opt.conv2d_variant != 17) || lines_per_run >= (1 << 20)) return hipSuccess;
+    if ((g.T * kh * kw < 60LL * cus && g_opt.conv2d_variant != 17 && g_opt.conv2d_variant != 18) || lines_per_run >= (1 << 20))
+        return hipSuccess;
     *taken = true;
+    // the split-operand instance: images, forward weights, and its larger ring must fit
+    size_t lds3 = (size_t)g.R * g.LW * kPitch3 + 4 * (kScratchFloats / 2 + kSpareFloats);
+    if (lds3 < wtmp) lds3 = wtmp;
+    if (!mode_b && !wadj && g_opt.conv2d_variant == 18 && lds3 <= 160 * 1024) {
+        if (cgs == 0) return launch_stream1<64, 3, 3, false, 0, false, true>(x, wgt, y, g, lds3, cus, s);
+        if (cgs == 1) return launch_stream1<64, 3, 3, false, 1, false, true>(x, wgt, y, g, lds3, cus, s);
+        return launch_stream1<64, 3, 3, false, 2, false, true>(x, wgt, y, g, lds3, cus, s);
+    }
     if (mode_b) return launch_stream<64, 1, 3, true, 1>(x, wgt, y, g, lds, cus, s);
     if (cgs == 0) return launch_stream<64, 3, 3, false, 0>(x, wgt, y, g, lds, cus, s);
     if (cgs == 1) return launch_stream<64, 3, 3, false, 1>(x, wgt, y, g, lds, cus, s);

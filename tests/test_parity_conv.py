@@ -332,14 +332,15 @@ def test_streaming_kernel_3x3(B, geom):
     wt = (r.standard_normal((cout, 64, 3, 3), dtype=np.float32) * 0.06).astype(np.float32)
     xi = workloads.integer_valued((n, 64, h, w), -4, 4, seed=h * w)
     wi = workloads.integer_valued((cout, 64, 3, 3), -3, 3, seed=cout)
-    B.sws_set_option("conv2d_variant", 17)
-    try:
-        _c2(B, x, wt, 1, 1, ph, pw, what="stream 3x3 %s" % (geom,))
-        y = to_host(B.sws_conv2d(to_gpu(xi), to_gpu(wi), 1, 1, ph, pw))
-    finally:
-        B.sws_set_option("conv2d_variant", 0)
-    ref, _ = oracle.conv2d(xi, wi, 1, 1, ph, pw)
-    assert np.array_equal(y.astype(np.float64), ref), "stream 3x3 integer-valued %s" % (geom,)
+    for variant in (17, 18):                          # fp32 matrix instructions; bf16 ones with split operands
+        B.sws_set_option("conv2d_variant", variant)
+        try:
+            _c2(B, x, wt, 1, 1, ph, pw, what="stream 3x3 %s variant %d" % (geom, variant))
+            y = to_host(B.sws_conv2d(to_gpu(xi), to_gpu(wi), 1, 1, ph, pw))
+        finally:
+            B.sws_set_option("conv2d_variant", 0)
+        ref, _ = oracle.conv2d(xi, wi, 1, 1, ph, pw)
+        assert np.array_equal(y.astype(np.float64), ref), "stream 3x3 integer-valued %s variant %d" % (geom, variant)
 
 
 @pytest.mark.parametrize("geom", [(2, 64, 34, 0), (1, 64, 500, 1), (3, 128, 1000, 2), (16, 64, 4096, 0), (5, 64, 3, 1),
@@ -370,13 +371,33 @@ def test_streaming_kernel_against_tile_kernel_full_size(B):
     ref, mag = oracle.conv2d(x, w, 1, 1, 1, 1)
     xg, wg = to_gpu(x), to_gpu(w)
     assert_within_tol(to_host(B.sws_conv2d(xg, wg, 1, 1, 1, 1)), ref, mag, "cfg4 streaming kernel")
-    for variant, name in ((2, "tile kernel"), (16, "scalar-read kernel")):
+    for variant, name in ((2, "tile kernel"), (16, "scalar-read kernel"), (18, "streaming kernel, split bf16 operands")):
         B.sws_set_option("conv2d_variant", variant)
         try:
             yt = to_host(B.sws_conv2d(xg, wg, 1, 1, 1, 1))
         finally:
             B.sws_set_option("conv2d_variant", 0)
-        assert_within_tol(yt, ref, mag, "cfg4 " + name)
+        worst = assert_within_tol(yt, ref, mag, "cfg4 " + name)
+        assert worst < 2e-6, "cfg4 %s: worst error ratio %g" % (name, worst)
+
+
+def test_split_operand_kernel_carries_every_bit(B):
+    """Inputs and weights whose magnitudes spread over six decades and whose mantissas use all 24 bits:
+    the bf16 x 3 evaluation must stay at fp32 accuracy (each operand is the exact sum of its three pieces;
+    only products below 2^-24 of a term are dropped)."""
+    r = _rng(4242)
+    x = (r.standard_normal((2, 64, 24, 30)) * 10.0 ** r.uniform(-3, 3, (2, 64, 24, 30))).astype(np.float32)
+    w = (r.standard_normal((64, 64, 3, 3)) * 10.0 ** r.uniform(-3, 3, (64, 64, 3, 3))).astype(np.float32)
+    ref, mag = oracle.conv2d(x, w, 1, 1, 1, 1)
+    worst = {}
+    for variant in (17, 18):
+        B.sws_set_option("conv2d_variant", variant)
+        try:
+            y = to_host(B.sws_conv2d(to_gpu(x), to_gpu(w), 1, 1, 1, 1))
+        finally:
+            B.sws_set_option("conv2d_variant", 0)
+        worst[variant] = assert_within_tol(y, ref, mag, "wide-range data, variant %d" % variant)
+    assert worst[18] < 1e-6 and worst[18] < 4 * worst[17] + 1e-7, worst
 
 
 def test_cfg1_correlation_full_size(B):
