@@ -75,7 +75,7 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
     constexpr int KT = KH * KW;
     constexpr int PITCH = CIN + kPad;
     constexpr int PB = X3 ? kPitch3 : PITCH * 4;      // bytes per staged position
-    static_assert(!X3 || (CIN == 64 && !MODE_B && !WADJ), "the split-operand path is built for 64-channel images");
+    static_assert(!X3 || (CIN == 64 && !MODE_B), "the split-operand path is built for 64-channel images");
     constexpr int CQ = CIN / 4;                       // input channels per wavefront
     constexpr int NCB = CQ / 8;                       // blocks of 8 channels among them
     // staging: a group is 16 columns x 4 channels (lane = column + 16 * channel); slot s of this wavefront
@@ -123,11 +123,12 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
     // spare area behind the scratch buffers instead — the ring is cleared once, so the zero padding
     // columns of every slot stay zero.  Rows: every lane inside the line writes (zero where the row ends).
     const bool st_wr = MODE_B ? st_in : st_colok;
-    // (X3: position st_pc, plane p, channel ci at p * 128 + 16 * ((ci >> 3) ^ (st_pc & 7)) + 2 * (ci & 7): the
-    // 16-byte groups of eight channels are permuted by the column, which spreads the 384-byte position
-    // pitch over the banks for the operand reads)
+    // (X3: position st_pc, plane p, channel ci at p * 128 + 16 * ((ci >> 3) ^ ((st_pc >> 1) & 7)) + 2 * (ci & 7):
+    // the 16-byte groups of eight channels are permuted by the column.  With the 384-byte position pitch,
+    // sixteen consecutive positions reading the same group then fall on sixteen different 16-byte bank
+    // groups: even and odd columns differ in bank bit 7, and eight columns of one parity in the permutation)
     const int st_dst = X3 ? st_pc * PB + 2 * (st_ci & 7) : (st_pc * PITCH + st_ci) * 4;
-    const int st_key = st_pc & 7, st_c8 = st_ci >> 3;
+    const int st_key = (st_pc >> 1) & 7, st_c8 = st_ci >> 3;
     char *const spare = (char *)(scratch + (X3 ? kScratchFloats / 2 : kScratchFloats));
     constexpr int SRC_STEP = 4 * CH_STEP, DST_STEP = 16 * CH_STEP;          // channels / bytes from one slot to the next
     auto line_begin = [&](int &l_n, int &l_pr, int &l_rel) {
@@ -161,16 +162,17 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
             for (int s = 0; s < XS; ++s) {
                 if (s < s0 || s >= s1) continue;
                 if (chg0 + s * CH_STEP < CIN / 4) {
-                    // x = x1 + x2 + x3 exactly: each piece is the bf16 nearest to what the earlier ones left
+                    // x = x1 + x2 + x3 exactly: the leading 8, the next 8 and the last 8 bits of the mantissa,
+                    // each the upper half of an fp32 word (a bf16 number), both differences exact
                     const float v = real ? xr[s] : 0.0f;
-                    const __bf16 v1 = (__bf16)v;
-                    const float r1 = v - (float)v1;
-                    const __bf16 v2 = (__bf16)r1;
-                    const __bf16 v3 = (__bf16)(r1 - (float)v2);
+                    const unsigned u1 = __float_as_uint(v) & 0xffff0000u;
+                    const float r1 = v - __uint_as_float(u1);
+                    const unsigned u2 = __float_as_uint(r1) & 0xffff0000u;
+                    const unsigned u3 = __float_as_uint(r1 - __uint_as_float(u2));
                     char *d = dst + 16 * ((st_c8 + s * (SRC_STEP / 8)) ^ st_key);
-                    *(__bf16 *)d = v1;
-                    *(__bf16 *)(d + 128) = v2;
-                    *(__bf16 *)(d + 256) = v3;
+                    *(unsigned short *)d = (unsigned short)(u1 >> 16);
+                    *(unsigned short *)(d + 128) = (unsigned short)(u2 >> 16);
+                    *(unsigned short *)(d + 256) = (unsigned short)(u3 >> 16);
                 }
             }
             return;
@@ -256,10 +258,10 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
                         const int ci = wq * CQ + 8 * half + e;
-                        const float *rd = wl + l32 * WP + ci * KT;
+                        const float *rd = WADJ ? wl + ci * (32 * KT) + l32 * KT : wl + l32 * WP + ci * KT;
 #pragma unroll
                         for (int t = 0; t < KT; ++t) {
-                            const float f = rd[t];
+                            const float f = rd[WADJ ? KT - 1 - t : t];
                             const __bf16 f1 = (__bf16)f;
                             const float r1 = f - (float)f1;
                             const __bf16 f2 = (__bf16)r1;
@@ -329,7 +331,7 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
                 if constexpr (X3) {
 #pragma unroll
                     for (int b = 0; b < KW; ++b)
-                        rb[a * KW + b] = (slot * g.LW + ow + b) * PB + 16 * (oct ^ ((ow + b) & 7));
+                        rb[a * KW + b] = (slot * g.LW + ow + b) * PB + 16 * (oct ^ (((ow + b) >> 1) & 7));
                 } else {
                     rb[a] = ((slot * g.LW + ow) * PITCH) * 4 + lane_const;
                 }
@@ -447,9 +449,9 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
             if constexpr (X3) {
                 const v8bf b8 = __builtin_bit_cast(v8bf, b4);
                 const int t = i / 3, p = i % 3;
-#pragma unroll
-                for (int q = 2 - p; q >= 0; --q)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w3[t][q], b8, acc, 0, 0, 0);
+                if (p == 0) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w3[t][2], b8, acc, 0, 0, 0);
+                if (p <= 1) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w3[t][1], b8, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w3[t][0], b8, acc, 0, 0, 0);
             } else {
                 const int t = i / NCB, cb = i % NCB;
                 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w[t][cb][0], b4.x, acc, 0, 0, 0);
@@ -622,7 +624,12 @@ hipError_t launch_conv2d_stream(const float *x, const float *wgt, float *y, int6
     // the split-operand instance: images, forward weights, and its larger ring must fit
     size_t lds3 = (size_t)g.R * g.LW * kPitch3 + 4 * (kScratchFloats / 2 + kSpareFloats);
     if (lds3 < wtmp) lds3 = wtmp;
-    if (!mode_b && !wadj && g_opt.conv2d_variant == 18 && lds3 <= 160 * 1024) {
+    if (!mode_b && g_opt.conv2d_variant != 17 && lds3 <= 160 * 1024) {
+        if (wadj) {
+            if (cgs == 0) return launch_stream1<64, 3, 3, false, 0, true, true>(x, wgt, y, g, lds3, cus, s);
+            if (cgs == 1) return launch_stream1<64, 3, 3, false, 1, true, true>(x, wgt, y, g, lds3, cus, s);
+            return launch_stream1<64, 3, 3, false, 2, true, true>(x, wgt, y, g, lds3, cus, s);
+        }
         if (cgs == 0) return launch_stream1<64, 3, 3, false, 0, false, true>(x, wgt, y, g, lds3, cus, s);
         if (cgs == 1) return launch_stream1<64, 3, 3, false, 1, false, true>(x, wgt, y, g, lds3, cus, s);
         return launch_stream1<64, 3, 3, false, 2, false, true>(x, wgt, y, g, lds3, cus, s);

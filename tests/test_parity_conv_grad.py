@@ -305,3 +305,25 @@ def test_graph_replay_of_the_adjoints_and_the_16_bit_sums(B):
             assert torch.equal(a, b), "replay %d differs from the eager result" % rep
         ref, _ = oracle.conv1d_grad_weight(x, to_host(gd), 3, 1, 1, 1, 1)
         assert np.array_equal(to_host(got[1]).astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("variant", [17, 18])
+@pytest.mark.parametrize("case", [(2, 64, 20, 20, 64, 3, 3, 1, 1, 1, 1), (3, 64, 9, 31, 128, 3, 3, 1, 1, 0, 1),
+                                  (1, 64, 33, 62, 64, 3, 3, 1, 1, 2, 2), (5, 64, 6, 6, 64, 3, 3, 1, 1, 1, 0)])
+def test_conv2d_grad_input_on_the_streaming_kernels(B, case, variant):
+    """grad-input of 64-channel 3 x 3 layers through the adjoint weight view of the weight-stationary
+    streaming kernels, forced on small problems: 17 = fp32 matrix instructions, 18 = bf16 ones with
+    split operands.  Random data within tolerance, integer data bit for bit."""
+    n, cin, h, wd, cout, kh, kw, sh, sw, ph, pw = case
+    _, w, g = _data2d(case, 900 + h, False)
+    _, wi, gi = _data2d(case, 901 + h, True)
+    B.sws_set_option("conv2d_variant", variant)
+    try:
+        gx = to_host(B.sws_conv2d_grad_input(to_gpu(g), to_gpu(w), h, wd, sh, sw, ph, pw))
+        gxi = to_host(B.sws_conv2d_grad_input(to_gpu(gi), to_gpu(wi), h, wd, sh, sw, ph, pw))
+    finally:
+        B.sws_set_option("conv2d_variant", 0)
+    rx, mx = oracle.conv2d_grad_input(g, w, h, wd, sh, sw, ph, pw)
+    assert_within_tol(gx, rx, mx, "streaming grad_input %s variant %d" % (case, variant))
+    rxi, _ = oracle.conv2d_grad_input(gi, wi, h, wd, sh, sw, ph, pw)
+    assert np.array_equal(gxi.astype(np.float64), rxi), "streaming grad_input, integers %s variant %d" % (case, variant)
