@@ -34,6 +34,17 @@
 // not.  So the per-step vector work is kept small — tap offsets are instruction immediates, the zero
 // padding columns of the ring are written once, the staging of a line uses one lane offset for all its
 // loads — and what remains is spread between the groups of four MFMAs.
+//
+// Split operands (template flag X3, images only).  An fp32 number is the exact sum of three bf16
+// numbers (the leading, middle and last 8 bits of its mantissa, each the upper half of an fp32 word),
+// and a product of two bf16 numbers is exact in fp32.  Of the nine piece products of x * w the three
+// smallest are below 2^-23 of the product; the other six, accumulated in fp32 by
+// v_mfma_f32_32x32x16_bf16, give the fp32 result to within less than one fp32 rounding per term — in
+// 6 instructions of 32 cycles per 16 channels and tap instead of 8 of 64 cycles.  The input is split when
+// a line is written to the ring (three bf16 planes per position, 384 bytes for 64 channels, 16-byte
+// channel groups permuted by the column so that the operand reads need no padding); the weights are
+// split once per run (108 registers).  The larger ring leaves room for one hand-over buffer only, so
+// this form has two workgroup barriers per block.
 #include "sws_internal.h"
 
 namespace sws {
