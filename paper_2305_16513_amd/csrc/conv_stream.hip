@@ -219,6 +219,20 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
             commit(xr0, p0r, r0r, 0, XS);
         }
     };
+    // the same at the start of a run, two lines' loads in flight at a time (X3)
+    auto stage_first = [&](int need) {
+        float xr1[XS];
+        int n1r = 0, p1r = 0, r1r = 0;
+        while (next_line + 1 < need) {
+            line_begin(n0r, p0r, r0r);
+            issue(xr0, n0r, p0r, 0, XS);
+            line_begin(n1r, p1r, r1r);
+            issue(xr1, n1r, p1r, 0, XS);
+            commit(xr0, p0r, r0r, 0, XS);
+            commit(xr1, p1r, r1r, 0, XS);
+        }
+        stage_sync(need);
+    };
 
     // ---- weights: A operands of all my MFMAs, loaded once per output-channel tile.  A lane's weights
     // lie 2304 bytes from its neighbour's, so the tile is first copied to LDS with coalesced loads (in
@@ -234,6 +248,54 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
         constexpr int PER = 32 * ROW / 4 / kThreads;  // 128-bit loads per thread and half tile
         static_assert(32 * ROW % (4 * kThreads) == 0 && ROW % 4 == 0, "half a tile divides over the threads");
         float *wl = lds;
+        constexpr int HALF = WADJ ? 32 * ROW : 32 * WP;        // floats of a staged half tile
+        if constexpr (X3) {
+            // the larger LDS of this form holds both halves side by side: one round of loads, every
+            // wavefront fills its registers at the same time
+            __syncthreads();                          // (the memory is the ring's: its last readers are done)
+#pragma unroll 1
+            for (int h = 0; h < 2; ++h) {
+                v4f v[PER];
+#pragma unroll
+                for (int u = 0; u < PER; ++u) {
+                    const int e = 4 * (threadIdx.x + u * kThreads);
+                    if (WADJ) {
+                        const int ci = e / (32 * KT), q = e - ci * (32 * KT);
+                        v[u] = *(const v4f_u *)(wgt + (unsigned)((ci * g.Cout + tile * 64 + 32 * h) * KT + q));
+                    } else {
+                        v[u] = *(const v4f_u *)(wgt + (unsigned)((tile * 64 + 32 * h) * ROW) + e);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < PER; ++u) {
+                    const int e = 4 * (threadIdx.x + u * kThreads);
+                    if (WADJ) {
+                        ((v4f *)(wl + h * HALF))[threadIdx.x + u * kThreads] = v[u];
+                    } else {
+                        float *d = wl + h * HALF + e + e / ROW;
+                        d[0] = v[u].x; d[1] = v[u].y; d[2] = v[u].z; d[3] = v[u].w;
+                    }
+                }
+            }
+            __syncthreads();
+            const float *wh = wl + wm * HALF;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int ci = wq * CQ + 8 * half + e;
+                const float *rd = WADJ ? wh + ci * (32 * KT) + l32 * KT : wh + l32 * WP + ci * KT;
+#pragma unroll
+                for (int t = 0; t < KT; ++t) {
+                    const float f = rd[WADJ ? KT - 1 - t : t];
+                    const __bf16 f1 = (__bf16)f;
+                    const float r1 = f - (float)f1;
+                    const __bf16 f2 = (__bf16)r1;
+                    w3[t][0][e] = f1;
+                    w3[t][1][e] = f2;
+                    w3[t][2][e] = (__bf16)(r1 - (float)f2);
+                }
+                __builtin_amdgcn_sched_barrier(0);            // (one channel's reads in flight at a time: registers)
+            }
+        } else
 #pragma unroll 1
         for (int h = 0; h < 2; ++h) {
             v4f v[PER];
@@ -266,22 +328,6 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
             __syncthreads();
             if (wm == h) {
                 if constexpr (X3) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int ci = wq * CQ + 8 * half + e;
-                        const float *rd = WADJ ? wl + ci * (32 * KT) + l32 * KT : wl + l32 * WP + ci * KT;
-#pragma unroll
-                        for (int t = 0; t < KT; ++t) {
-                            const float f = rd[WADJ ? KT - 1 - t : t];
-                            const __bf16 f1 = (__bf16)f;
-                            const float r1 = f - (float)f1;
-                            const __bf16 f2 = (__bf16)r1;
-                            w3[t][0][e] = f1;
-                            w3[t][1][e] = f2;
-                            w3[t][2][e] = (__bf16)(r1 - (float)f2);
-                        }
-                        __builtin_amdgcn_sched_barrier(0);            // (one channel's reads in flight at a time: registers)
-                    }
                 } else {
 #pragma unroll
                     for (int cb = 0; cb < NCB; ++cb)
@@ -394,7 +440,8 @@ __global__ __launch_bounds__(kThreads) void conv_stream_kernel(const float *__re
         // rewind the staging state to the current block's first line
         const int lo_c = MODE_B ? k : __builtin_amdgcn_readfirstlane(fdiv(32 * k, g.inv_Wo));
         next_line = img_base + lo_c; st_n = n; st_pr = lo_c;
-        stage_sync(img_base + hi_of(k, q1));
+        if constexpr (X3) stage_first(img_base + hi_of(k, q1));
+        else stage_sync(img_base + hi_of(k, q1));
     }
     bases(k, img_base, rb, pok, pp);
     long long seg_end = (long long)(ct + 1) * g.N * g.BPI;
@@ -634,7 +681,7 @@ hipError_t launch_conv2d_stream(const float *x, const float *wgt, float *y, int6
     *taken = true;
     // the split-operand instance: images, forward weights, and its larger ring must fit
     size_t lds3 = (size_t)g.R * g.LW * kPitch3 + 4 * (kScratchFloats / 2 + kSpareFloats);
-    if (lds3 < wtmp) lds3 = wtmp;
+    if (lds3 < 2 * wtmp) lds3 = 2 * wtmp;             // the whole weight tile passes through LDS at once
     if (!mode_b && g_opt.conv2d_variant != 17 && lds3 <= 160 * 1024) {
         if (wadj) {
             if (cgs == 0) return launch_stream1<64, 3, 3, false, 0, true, true>(x, wgt, y, g, lds3, cus, s);
