@@ -6,10 +6,12 @@
 // as a cross-check of the tuned kernel — for plain +, max and min.
 //
 // Same scheme as the tuned scan kernel (the block form of Section 3, Algorithm 2): a wavefront
-// owns a tile of 512 (1024 for w > 309) consecutive elements of a row, cut into segments of S = w - 1 elements
+// owns a tile of 512 (1024 for w > 208) consecutive elements of a row, cut into segments of S = w - 1 elements
 // counted from the tile origin.  For every element it forms
 //     Pre[q] = x[segment start] (+) ... (+) x[q]      Suf[q] = x[q] (+) ... (+) x[segment end]
-// and every output is one more operation:  y[q] = Suf[q] (+) Pre[q + S].
+// and every output is one more operation:  y[q] = Suf[q] (+) Pre[q + S] — done in the lane's own chunk
+// (Suf stays in registers, Pre[q + S ..] is read back from LDS at the window's offset), so that a tile
+// needs one set of LDS planes, not two.
 // A lane scans 8 (16) consecutive elements; lane totals are joined by segmented log-step scans across
 // the wavefront (flag = "my elements contain a segment boundary"), then the in-lane scans run
 // again seeded with the carries.  Segment resets are selects, so nothing is assumed about the
@@ -23,7 +25,9 @@ namespace {
 
 // Two tile shapes: 8 elements per lane (tile 512, 4 wavefronts per workgroup) for short windows,
 // 16 per lane (tile 1024, 2 wavefronts per workgroup: the same LDS per workgroup) for long ones.
-constexpr int kSmallMaxW = 309;                      // measured break-even of the two shapes (pairs, 16384-long rows)
+// Pairs on [16384,16384], % of HBM peak, tile 512 / 1024: w = 16 67 / 63, 128 67 / 61, 200 60 / 59,
+// 255 52 / 58, 400 28 / 49.
+constexpr int kSmallMaxW = 208;                      // measured break-even of the two shapes (pairs, 16384-long rows)
 constexpr int kGenericMaxW = 961;                    // tile 1024: at least 64 outputs per tile
 
 __device__ __forceinline__ void wave_lds_sync()
@@ -76,8 +80,9 @@ __global__ __launch_bounds__(kPer == 8 ? 256 : 128) void slide_generic_kernel(co
     // with what y already holds (an earlier link of a chain of windows, which covers older elements).
     constexpr int NP = O::NP;
     constexpr int kTile = 64 * kPer, kWavesPerWg = kPer == 8 ? 4 : 2;
-    // planes [0, NP): the inputs, later Pre; planes [NP, 2 NP): Suf.  One private slice per wavefront.
-    __shared__ __attribute__((aligned(16))) float lds[kWavesPerWg][2 * NP][kTile];
+    // planes [0, NP): the inputs, then Pre, then the results (Suf never leaves the registers).  One
+    // private slice per wavefront.
+    __shared__ __attribute__((aligned(16))) float lds[kWavesPerWg][NP][kTile];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -205,42 +210,66 @@ __global__ __launch_bounds__(kPer == 8 ? 256 : 128) void slide_generic_kernel(co
         for (int p = 0; p < NP; ++p) suf[e][p] = carry_s[p];
     }
 
-    // ---- exchange: Pre over the input planes, Suf beside them
+    // ---- exchange: Pre goes to LDS over the input planes; Suf stays in registers
 #pragma unroll
     for (int p = 0; p < NP; ++p)
 #pragma unroll
         for (int h = 0; h < kPer / 4; ++h) {
             const int pos = gpos<kPer>(kPer * lane + 4 * h);
             *(v4f *)(&L[p][pos]) = (v4f){pre[4 * h][p], pre[4 * h + 1][p], pre[4 * h + 2][p], pre[4 * h + 3][p]};
-            *(v4f *)(&L[NP + p][pos]) = (v4f){suf[4 * h][p], suf[4 * h + 1][p], suf[4 * h + 2][p], suf[4 * h + 3][p]};
         }
     wave_lds_sync();
 
-    // ---- combine y[q] = Suf[q] (+) Pre[q + S] on strips, store
+    // ---- combine in the lane's own chunk: y[q + e] = Suf[q + e] (+) Pre[q + e + S], q = kPer * lane.  The
+    //      kPer elements from q + S on lie in kPer/4 + 1 aligned groups (S mod 4 is the same for every
+    //      lane); groups past the tile belong to outputs that are not stored and are read clamped.
+    const int sh = S & 3;
+    float o[kPer][NP];
+    {
+        const int g0 = (kPer * lane + S) >> 2;
+        float wv[kPer + 4][NP];
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+#pragma unroll
+            for (int h = 0; h <= kPer / 4; ++h) {
+                const int gq = g0 + h < kTile / 4 ? g0 + h : kTile / 4 - 1;
+                const v4f v = *(const v4f *)(&L[p][gpos<kPer>(4 * gq)]);
+                wv[4 * h][p] = v.x; wv[4 * h + 1][p] = v.y; wv[4 * h + 2][p] = v.z; wv[4 * h + 3][p] = v.w;
+            }
+#pragma unroll
+        for (int e = 0; e < kPer; ++e) {
+            float b[NP];
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+                b[p] = sh == 0 ? wv[e][p] : (sh == 1 ? wv[e + 1][p] : (sh == 2 ? wv[e + 2][p] : wv[e + 3][p]));
+            O::f(suf[e], b, o[e]);
+        }
+    }
+    wave_lds_sync();                                 // every lane has read its Pre values: the planes are free again
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+#pragma unroll
+        for (int h = 0; h < kPer / 4; ++h) {
+            const int pos = gpos<kPer>(kPer * lane + 4 * h);
+            *(v4f *)(&L[p][pos]) = (v4f){o[4 * h][p], o[4 * h + 1][p], o[4 * h + 2][p], o[4 * h + 3][p]};
+        }
+    wave_lds_sync();
+
+    // ---- results back as strips, coalesced stores
     int lim = lo - t0;
     if (lim > tout) lim = tout;
-    const int sh = S & 3;                            // Pre[q + S ..] straddles two aligned groups unless sh == 0
 #pragma unroll
     for (int j = 0; j < kTile / 256; ++j) {
         const int q = 256 * j + 4 * lane;
         if (q >= lim) continue;
-        const int g0 = (q + S) >> 2;                 // q + S < kTile for every stored output
-        const int g1 = g0 + 1 < kTile / 4 ? g0 + 1 : kTile / 4 - 1;
-        float a4[4][NP], b4[4][NP], o4[4][NP];
+        float o4[4][NP];
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
-            const v4f s4 = *(const v4f *)(&L[NP + p][gpos<kPer>(q)]);
-            const v4f lo4 = *(const v4f *)(&L[p][gpos<kPer>(4 * g0)]);
-            const v4f hi4 = *(const v4f *)(&L[p][gpos<kPer>(4 * g1)]);
-            a4[0][p] = s4.x; a4[1][p] = s4.y; a4[2][p] = s4.z; a4[3][p] = s4.w;
-            const float w8[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-                b4[c][p] = sh == 0 ? w8[c] : (sh == 1 ? w8[c + 1] : (sh == 2 ? w8[c + 2] : w8[c + 3]));
+            const v4f v = *(const v4f *)(&L[p][gpos<kPer>(q)]);
+            o4[0][p] = v.x; o4[1][p] = v.y; o4[2][p] = v.z; o4[3][p] = v.w;
         }
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            O::f(a4[c], b4[c], o4[c]);
             if (accum && q + c < lim) {
                 float old[NP], t2[NP];
 #pragma unroll
@@ -296,7 +325,7 @@ template <class O>
 hipError_t launch_generic_tiles(const float *x0, const float *x1, float *y0, float *y1, int64_t rows, int len, int lo,
                                 int w, float scale, int pitch, int accum, hipStream_t s)
 {
-    const bool small = w <= kSmallMaxW;
+    const bool small = w <= (g_opt.slide_group > 0 ? g_opt.slide_group : kSmallMaxW);      // (slide_group: A/B of the break-even)
     const int S = w - 1, tout = (small ? 512 : 1024) - S, waves = small ? 4 : 2;
     const int64_t tiles_per_row = (lo + tout - 1) / tout;
     const int64_t n_tiles = rows * tiles_per_row;
