@@ -325,7 +325,9 @@ template <class O>
 hipError_t launch_generic_tiles(const float *x0, const float *x1, float *y0, float *y1, int64_t rows, int len, int lo,
                                 int w, float scale, int pitch, int accum, hipStream_t s)
 {
-    const bool small = w <= (g_opt.slide_group > 0 ? g_opt.slide_group : kSmallMaxW);      // (slide_group: A/B of the break-even)
+    // (slide_group: A/B of the break-even; the 512-tile is never taken above w = 448, where it has 64 outputs left)
+    const int small_max = g_opt.slide_group > 0 ? (g_opt.slide_group < 448 ? (int)g_opt.slide_group : 448) : kSmallMaxW;
+    const bool small = w <= small_max;
     const int S = w - 1, tout = (small ? 512 : 1024) - S, waves = small ? 4 : 2;
     const int64_t tiles_per_row = (lo + tout - 1) / tout;
     const int64_t n_tiles = rows * tiles_per_row;
