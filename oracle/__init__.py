@@ -31,6 +31,7 @@ from .ref import (  # noqa: F401
     PAD_PERIODIC,
     PAD_SHRINK,
     slide1d,
+    pool2d_padded,
     slide1d_padded,
     slide1d_pair,
     threads,

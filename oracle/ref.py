@@ -48,6 +48,9 @@ def _load():
         lib.sws_ref_pool2d_ex.restype = ctypes.c_int
         lib.sws_ref_pool2d_ex.argtypes = [ctypes.c_int, _fp, _dp, _dp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32,
                                           _i32, _i32, _i32, _i32, ctypes.c_int, _f64]
+        lib.sws_ref_pool2d_padded.restype = ctypes.c_int
+        lib.sws_ref_pool2d_padded.argtypes = [ctypes.c_int, _fp, _dp, _dp, _i64, _i64, _i64, _i32, _i32, _i32, _i32,
+                                              _i32, _i32, _i32, _i32, ctypes.c_int, _f64]
         lib.sws_ref_slide1d_padded.restype = ctypes.c_int
         lib.sws_ref_slide1d_padded.argtypes = [ctypes.c_int, _fp, _dp, _dp, _i64, _i64, _i32, _i32, _i32,
                                                ctypes.c_int, _f64]
@@ -131,6 +134,28 @@ def round16(y, dtype):
 
 
 PAD_IDENTITY, PAD_MIRROR, PAD_PERIODIC, PAD_EDGE, PAD_SHRINK = 0, 1, 2, 3, 4
+
+
+def pool2d_padded(op, x, kh, kw, sh=1, sw=1, pads=(0, 0, 0, 0), mode=PAD_IDENTITY, scale=1.0):
+    """x: [..., H, W] float32, pads = (top, left, bottom, right) -> (y, abs_sum) [..., Ho, Wo] float64:
+    pooling over planes extended on their four sides by the rule of `mode` (identity, mirror,
+    periodic or edge)."""
+    x = _f32(x)
+    h, w = x.shape[-2:]
+    lead = x.shape[:-2]
+    planes = int(np.prod(lead)) if lead else 1
+    pt, pl, pb, pr = pads
+    he, we = h + pt + pb, w + pl + pr
+    if kh > he or kw > we:
+        raise ValueError("window larger than the extended plane")
+    ho, wo = (he - kh) // sh + 1, (we - kw) // sw + 1
+    y = np.empty(lead + (ho, wo), np.float64)
+    s = np.empty(lead + (ho, wo), np.float64)
+    rc = _load().sws_ref_pool2d_padded(op, _ptr_f(x), _ptr_d(y), _ptr_d(s), planes, h, w, kh, kw, sh, sw, pt, pl, pb, pr,
+                                       mode, float(scale))
+    if rc:
+        raise ValueError("sws_ref_pool2d_padded rejected its arguments")
+    return y, s
 
 
 def slide1d_padded(op, x, w, pad_left, pad_right, mode, scale=1.0):

@@ -32,6 +32,9 @@
  *                    named in Section 3: padding, mirroring, periodicity; plus edge
  *                    replication).  Every window element's index is mapped back into
  *                    the row by the rule of the mode, then combined as in Eq. 3.
+ *   sws_ref_pool2d_padded  the same boundary conditions in two dimensions: Eq. 3 over kh x kw
+ *                    windows of planes extended on their four sides, both indices of every
+ *                    window cell mapped back into the plane by the rule of the mode.
  *   sws_ref_slide1d_pair  Eq. 3 with the pair operator of Section 2.4, Eq. 8:
  *                    (u_i, v_i) (+) (u_j, v_j) = (u_i*u_j, u_j*v_i + v_j), i older.
  *                    Non-commutative; folded strictly left to right.
@@ -334,6 +337,60 @@ int sws_ref_slide1d_padded(int op, const float *x, double *y, double *abs_sum, i
             y[r * lo + i] = op == REF_ADD ? acc * f : acc;
             if (abs_sum) abs_sum[r * lo + i] = op == REF_ADD ? mag * fabs(f) : mag;
         }
+    }
+    return 0;
+}
+
+/* Index of the physical element that virtual index p (0 <= p < len is physical) of a line extended
+ * by the rule `mode` stands for; -1: the operator's identity (mode 0). */
+static int64_t map_index(int64_t p, int64_t len, int mode)
+{
+    if (p >= 0 && p < len) return p;
+    if (mode == 1) return p < 0 ? -p : 2 * (len - 1) - p;            /* mirror, end elements not repeated */
+    if (mode == 2) return p < 0 ? p + len : p - len;                 /* periodic */
+    if (mode == 3) return p < 0 ? 0 : len - 1;                       /* edge */
+    return -1;
+}
+
+/* 2-D pooling (Section 2.3) over planes extended on their four sides by a boundary condition of
+ * Section 3 (mode 0 identity padding, 1 mirror, 2 periodic, 3 edge replication):
+ *   y[p,ho,wo] = scale_if_add * (+)_{a<kh, b<kw} X[p, ho*sh - pad_top + a, wo*sw - pad_left + b],
+ * X = x inside the plane, the mapped cell (or the identity) outside.  Row-major window order.
+ * x: planes*H*W floats; y, abs_sum: planes*Ho*Wo doubles, Ho = (H+pad_top+pad_bottom-kh)/sh + 1. */
+int sws_ref_pool2d_padded(int op, const float *x, double *y, double *abs_sum, int64_t planes, int64_t H, int64_t W,
+                          int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t pad_top, int32_t pad_left,
+                          int32_t pad_bottom, int32_t pad_right, int mode, double scale)
+{
+    if (op < 0 || op > 2 || mode < 0 || mode > 3 || planes < 0 || H < 1 || W < 1 || kh < 1 || kw < 1 || sh < 1 || sw < 1)
+        return 1;
+    if (pad_top < 0 || pad_left < 0 || pad_bottom < 0 || pad_right < 0) return 1;
+    if (mode == 1 && (pad_top > H - 1 || pad_bottom > H - 1 || pad_left > W - 1 || pad_right > W - 1)) return 1;
+    if (mode == 2 && (pad_top > H || pad_bottom > H || pad_left > W || pad_right > W)) return 1;
+    const int64_t He = H + pad_top + pad_bottom, We = W + pad_left + pad_right;
+    if (kh > He || kw > We) return 1;
+    const int64_t Ho = (He - kh) / sh + 1, Wo = (We - kw) / sw + 1;
+    if (planes > 0 && (!x || !y)) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t p = 0; p < planes; ++p) {
+        const float *xp = x + p * H * W;
+        for (int64_t ho = 0; ho < Ho; ++ho)
+            for (int64_t wo = 0; wo < Wo; ++wo) {
+                double acc = 0.0, mag = 0.0;
+                int64_t have = 0;
+                for (int32_t a = 0; a < kh; ++a)
+                    for (int32_t b = 0; b < kw; ++b) {
+                        const int64_t r = map_index(ho * sh - pad_top + a, H, mode);
+                        const int64_t c = map_index(wo * sw - pad_left + b, W, mode);
+                        if (r < 0 || c < 0) continue;                /* identity element */
+                        const double v = (double)xp[r * W + c];
+                        acc = have ? combine(op, acc, v) : v;
+                        ++have;
+                        mag += fabs(v);
+                    }
+                if (!have) acc = op == REF_ADD ? 0.0 : (op == REF_MAX ? -INFINITY : INFINITY);
+                y[(p * Ho + ho) * Wo + wo] = op == REF_ADD ? acc * scale : acc;
+                if (abs_sum) abs_sum[(p * Ho + ho) * Wo + wo] = op == REF_ADD ? mag * fabs(scale) : mag;
+            }
     }
     return 0;
 }

@@ -995,3 +995,66 @@ def test_avgpool2d_grad_is_the_adjoint_of_the_pinned_forward_pooling(geom, div_v
     if sh == 1 and sw == 1 and not div_valid:
         slid, _ = oracle.pool2d_ex(oracle.OP_ADD, gy, kh, kw, 1, 1, (kh - 1 - ph, kw - 1 - pw, kh - 1 - ph, kw - 1 - pw), False, 0.5)
         assert np.array_equal(slid, gx)
+
+
+# ----------------------------------------------------------------------------- P18
+# The boundary conditions of Section 3 in two dimensions (sws_ref_pool2d_padded).
+def test_pool2d_padded_hand_enumerated():
+    x = np.array([[1, 2, 3], [4, 5, 6]], np.float32)
+    # one row above and one column in front, 2 x 2 windows; extended planes written out by hand:
+    #   mirror   5 4 5 6     periodic 6 4 5 6     edge 1 1 2 3     identity . . . .
+    #            2 1 2 3              3 1 2 3          1 1 2 3              . 1 2 3
+    #            5 4 5 6              6 4 5 6          4 4 5 6              . 4 5 6
+    want_add = {oracle.PAD_MIRROR: [[12, 12, 16], [12, 12, 16]], oracle.PAD_PERIODIC: [[14, 12, 16], [14, 12, 16]],
+                oracle.PAD_EDGE: [[4, 6, 10], [10, 12, 16]], oracle.PAD_IDENTITY: [[1, 3, 5], [5, 12, 16]]}
+    want_max = {oracle.PAD_MIRROR: [[5, 5, 6], [5, 5, 6]], oracle.PAD_PERIODIC: [[6, 5, 6], [6, 5, 6]],
+                oracle.PAD_EDGE: [[1, 2, 3], [4, 5, 6]], oracle.PAD_IDENTITY: [[1, 2, 3], [4, 5, 6]]}
+    for mode in want_add:
+        y, m = oracle.pool2d_padded(OP_ADD, x, 2, 2, 1, 1, (1, 1, 0, 0), mode)
+        assert y.tolist() == want_add[mode] and m.tolist() == want_add[mode]
+        y, _ = oracle.pool2d_padded(OP_MAX, x, 2, 2, 1, 1, (1, 1, 0, 0), mode)
+        assert y.tolist() == want_max[mode]
+    y, _ = oracle.pool2d_padded(OP_MIN, -x, 2, 2, 2, 2, (0, 0, 2, 1), oracle.PAD_EDGE, 1.0)
+    # -x with two rows below and one column behind (edge): rows -1 -2 -3 -3 / -4 -5 -6 -6 / -4.. / -4..; stride 2
+    assert y.tolist() == [[-5.0, -6.0], [-5.0, -6.0]]
+
+
+@pytest.mark.parametrize("mode,np_mode", [(1, "reflect"), (2, "wrap"), (3, "edge"), (0, "constant")])
+@pytest.mark.parametrize("geom", [(3, 3, 1, 1, (1, 1, 1, 1)), (2, 4, 2, 1, (0, 3, 1, 0)), (5, 1, 1, 2, (4, 0, 0, 0)),
+                                  (1, 6, 3, 3, (0, 2, 0, 5)), (4, 4, 4, 4, (2, 2, 2, 2)), (7, 7, 1, 1, (6, 6, 6, 6))])
+def test_pool2d_padded_equals_pooling_of_an_explicitly_extended_plane(mode, np_mode, geom):
+    """numpy.pad writes the extended planes out (a library routine as a second opinion on the index rules
+    in both dimensions); the pinned unpadded pooling then runs over them."""
+    kh, kw, sh, sw, pads = geom
+    pt, pl, pb, pr = pads
+    r = _rng(180 + kh * 10 + kw + mode)
+    x = r.standard_normal((2, 3, 9, 11), dtype=np.float32)
+    for op in (OP_ADD, OP_MAX, OP_MIN):
+        fill = {OP_ADD: 0.0, OP_MAX: -np.inf, OP_MIN: np.inf}[op]
+        kwargs = {"constant_values": fill} if mode == 0 else {}
+        ext = np.pad(x, ((0, 0), (0, 0), (pt, pb), (pl, pr)), mode=np_mode, **kwargs).astype(np.float32)
+        y, m = oracle.pool2d_padded(op, x, kh, kw, sh, sw, pads, mode, 0.5)
+        with np.errstate(invalid="ignore"):
+            ref, _ = oracle.pool2d(op, ext, kh, kw, sh, sw, 0, 0, 0.5)
+        assert np.array_equal(y, ref)
+
+
+def test_pool2d_padded_reduces_to_the_other_pooling_functions_and_to_rows():
+    r = _rng(181)
+    x = r.standard_normal((1, 3, 12, 14), dtype=np.float32)
+    for op in (OP_ADD, OP_MAX):
+        y, m = oracle.pool2d_padded(op, x, 3, 3, 2, 2, (1, 1, 1, 1), oracle.PAD_IDENTITY, 1 / 9)
+        ref, mag = oracle.pool2d(op, x, 3, 3, 2, 2, 1, 1, 1 / 9)
+        assert np.array_equal(y, ref) and np.array_equal(m, mag)
+        # windows of one row: the rows of a plane under the 1-D boundary rule
+        for mode in range(4):
+            y, _ = oracle.pool2d_padded(op, x, 1, 5, 1, 1, (0, 3, 0, 2), mode, 0.2)
+            rows, _ = oracle.slide1d_padded(op, x.reshape(36, 14), 5, 3, 2, mode, 0.2)
+            assert np.array_equal(y.reshape(36, -1), rows)
+    # periodic with pads k - 1 behind: one output per cell and every cell counted kh * kw times
+    y, _ = oracle.pool2d_padded(OP_ADD, x, 3, 4, 1, 1, (0, 0, 2, 3), oracle.PAD_PERIODIC)
+    assert y.shape == x.shape and np.allclose(y.sum(axis=(2, 3)), 12 * x.astype(np.float64).sum(axis=(2, 3)), atol=1e-10)
+    with pytest.raises(ValueError):
+        oracle.pool2d_padded(OP_ADD, x, 3, 3, 1, 1, (12, 0, 0, 0), oracle.PAD_MIRROR)      # mirror reaches past the plane
+    with pytest.raises(ValueError):
+        oracle.pool2d_padded(OP_ADD, x, 3, 3, 1, 1, (0, 0, 0, 15), oracle.PAD_PERIODIC)
