@@ -286,6 +286,20 @@ def sweeps_table(torch, B, workloads, iters=20):
             del y
     del u, v
     torch.cuda.empty_cache()
+    # the same in two dimensions: configuration 3's planes extended by k/2 mirrored rows and columns on every side
+    x3 = g(workloads.make(3)[0])
+    for op, opn in ((0, "avg"), (1, "max")):
+        for k, st in ((3, 1), (3, 2), (7, 1)):
+            ho = (112 + 2 * (k // 2) - k) // st + 1
+            y = torch.empty(32, 64, ho, ho, device="cuda")
+            ms = time_launches(torch, lambda: B.sws_pool2d_padded(op, x3, k, k, st, st, (k // 2,) * 4, B.SWS_PAD_MIRROR,
+                                                                  1.0 / (k * k), y=y), iters)
+            nb = 4 * (x3.numel() + y.numel())
+            out["same_size_pooling"]["cfg3_%s_%dx%d_s%d_mirror" % (opn, k, k, st)] = {
+                "ms": round(ms, 4), "GBps": round(nb / ms / 1e6, 1), "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+            del y
+    del x3
+    torch.cuda.empty_cache()
     # configuration 5's sliding sums on 16-bit storage (fp32 arithmetic, one rounding): half the bytes
     x16 = g(workloads.make(5)[0]).to(torch.bfloat16)
     for dt, dn in ((torch.bfloat16, "bf16"), (torch.float16, "f16")):
@@ -564,6 +578,15 @@ def run_only(torch, B, workloads, name, steps, cold=False):
         gy = torch.empty(32, 64, ho, ho, device="cuda").normal_()
         gx = torch.empty_like(x3)
         fn = lambda: B.sws_maxpool2d_grad(x3, gy, 3, 3, s, s, 1, 1, gx=gx)
+    elif name.startswith("padded_cfg3_"):                 # padded_cfg3_<avg|max>_<mirror|periodic|edge>_k<k>_s<s>
+        _, _, opn, mn, kn, sn = name.split("_")
+        k, st = int(kn[1:]), int(sn[1:])
+        mode = {"mirror": B.SWS_PAD_MIRROR, "periodic": B.SWS_PAD_PERIODIC, "edge": B.SWS_PAD_EDGE}[mn]
+        x3 = g(workloads.make(3)[0])
+        ho = (112 + 2 * (k // 2) - k) // st + 1
+        y = torch.empty(32, 64, ho, ho, device="cuda")
+        op = 1 if opn == "max" else 0
+        fn = rotating(x3, y)(lambda xx, yy: B.sws_pool2d_padded(op, xx, k, k, st, st, (k // 2,) * 4, mode, 1.0 / (k * k), y=yy))
     elif name.startswith("cfg3_"):
         x3 = g(workloads.make(3)[0])
         s = int(name[-1])

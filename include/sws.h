@@ -187,6 +187,28 @@ sws_status sws_pool2d_ex(sws_op op, const float *x, float *y, int64_t N, int64_t
                          int32_t pad_top, int32_t pad_left, int32_t pad_bottom, int32_t pad_right,
                          sws_divisor divisor, float scale, sws_stream_t stream);
 
+/* 2-D pooling over planes extended by the boundary conditions of Section 3 (padding with the
+ * identity, mirroring, periodicity; also the repeated edge and shrinking windows) on all four
+ * sides — sws_slide1d_padded carried to two dimensions; the rule applies to rows and columns
+ * independently (a corner cell mirrors / wraps on both axes):
+ *
+ *   y[n,c,ho,wo] = scale * (+)_{a<kh} (+)_{b<kw} xe[n,c, ho*sh + a, wo*sw + b]
+ *   xe[n,c,i,j]  = x[n,c, src(i - pad_top, H), src(j - pad_left, W)],  0 <= i < H + pad_top + pad_bottom,
+ *   Ho = (H + pad_top + pad_bottom - kh)/sh + 1,  Wo = (W + pad_left + pad_right - kw)/sw + 1
+ *
+ * with src the index rule of `mode` as in sws_pad_mode (IDENTITY: the cell holds the identity of
+ * op; SHRINK: identity, and an ADD result is divided by the number of window cells inside the
+ * plane, i.e. sws_pool2d_ex with SWS_DIV_REAL_CELLS).  scale multiplies ADD results only.
+ *   x : device, N*C*H*W floats          y : device, N*C*Ho*Wo floats
+ * Errors: as sws_pool2d; INVALID_ARG if H or W < 1, a pad is negative, the window exceeds the
+ * extended plane, the mode is unknown, a MIRROR pad exceeds the extent of its axis minus 1, a
+ * PERIODIC pad exceeds that extent, or a SHRINK pad is not smaller than the window on its axis;
+ * UNSUPPORTED if the extended plane has more than 2^31 - 1 - 65536 cells. */
+sws_status sws_pool2d_padded(sws_op op, const float *x, float *y, int64_t N, int64_t C, int64_t H,
+                             int64_t W, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                             int32_t pad_top, int32_t pad_left, int32_t pad_bottom, int32_t pad_right,
+                             sws_pad_mode mode, float scale, sws_stream_t stream);
+
 /* The adjoint of average pooling (Section 2.3's pooling with the + operator, training side): of
  * sws_pool2d_ex with SWS_OP_ADD, padding ph on top and bottom and pw left and right, and the same
  * divisor and scale.  With loss = sum(gy * y),

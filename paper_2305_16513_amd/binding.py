@@ -19,7 +19,7 @@ _lib = None
 
 _i64, _i32, _f32, _vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
 
-EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_maxpool2d_grad", "sws_avgpool2d_grad", "sws_pool2d_16", "sws_pool2d_ex", "sws_conv1d", "sws_conv1d_16", "sws_conv1d_grad_input", "sws_conv1d_grad_weight", "sws_conv2d", "sws_conv2d_grad_input", "sws_conv2d_grad_weight", "sws_copy", "sws_out_len",
+EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_maxpool2d_grad", "sws_avgpool2d_grad", "sws_pool2d_16", "sws_pool2d_ex", "sws_pool2d_padded", "sws_conv1d", "sws_conv1d_16", "sws_conv1d_grad_input", "sws_conv1d_grad_weight", "sws_conv2d", "sws_conv2d_grad_input", "sws_conv2d_grad_weight", "sws_copy", "sws_out_len",
            "sws_status_string", "sws_set_option", "sws_version")
 
 
@@ -59,6 +59,9 @@ def lib():
         L.sws_pool2d_ex.restype = ctypes.c_int
         L.sws_pool2d_ex.argtypes = [ctypes.c_int, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32,
                                     _i32, _i32, _i32, _i32, ctypes.c_int, _f32, _vp]
+        L.sws_pool2d_padded.restype = ctypes.c_int
+        L.sws_pool2d_padded.argtypes = [ctypes.c_int, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32,
+                                        _i32, _i32, _i32, _i32, ctypes.c_int, _f32, _vp]
         L.sws_conv1d.restype = ctypes.c_int
         L.sws_conv1d.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _vp]
         L.sws_conv1d_16.restype = ctypes.c_int
@@ -280,6 +283,21 @@ def sws_pool2d_ex(op, x, kh, kw, sh=1, sw=1, pads=(0, 0, 0, 0), divisor=SWS_DIV_
     y = _out(y, (n, c, ho, wo), x)
     _check(lib().sws_pool2d_ex(op, x.data_ptr(), y.data_ptr(), n, c, h, wd, kh, kw, sh, sw, pt, pl, pb, pr, divisor,
                                scale, _stream(stream)), "sws_pool2d_ex")
+    return y
+
+
+def sws_pool2d_padded(op, x, kh, kw, sh=1, sw=1, pads=(0, 0, 0, 0), mode=0, scale=1.0, y=None, stream=None):
+    """x [N, C, H, W], pads = (top, left, bottom, right), mode = SWS_PAD_* -> y [N, C, Ho, Wo]: pooling over
+    planes extended on four sides by the boundary rule `mode`."""
+    _dev(x, "x")
+    n, c, h, wd = x.shape
+    pt, pl, pb, pr = pads
+    ho, wo = (h + pt + pb - kh) // sh + 1, (wd + pl + pr - kw) // sw + 1
+    if ho < 1 or wo < 1 or min(pads) < 0:
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_pool2d_padded")
+    y = _out(y, (n, c, ho, wo), x)
+    _check(lib().sws_pool2d_padded(op, x.data_ptr(), y.data_ptr(), n, c, h, wd, kh, kw, sh, sw, pt, pl, pb, pr, mode,
+                                   scale, _stream(stream)), "sws_pool2d_padded")
     return y
 
 

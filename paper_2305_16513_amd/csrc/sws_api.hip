@@ -251,6 +251,34 @@ sws_status sws_pool2d_ex(sws_op op, const float *x, float *y, int64_t N, int64_t
                                        divisor == SWS_DIV_REAL_CELLS ? 1 : 0, (hipStream_t)stream));
 }
 
+sws_status sws_pool2d_padded(sws_op op, const float *x, float *y, int64_t N, int64_t C, int64_t H, int64_t W,
+                             int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t pad_top, int32_t pad_left,
+                             int32_t pad_bottom, int32_t pad_right, sws_pad_mode mode, float scale, sws_stream_t stream)
+{
+    if (!valid_op((int)op) || N < 0 || C < 0 || H < 1 || W < 1) return SWS_ERR_INVALID_ARG;
+    if (kh < 1 || kw < 1 || sh < 1 || sw < 1) return SWS_ERR_INVALID_ARG;
+    if (pad_top < 0 || pad_left < 0 || pad_bottom < 0 || pad_right < 0) return SWS_ERR_INVALID_ARG;
+    if ((int)mode < SWS_PAD_IDENTITY || (int)mode > SWS_PAD_SHRINK) return SWS_ERR_INVALID_ARG;
+    if (mode == SWS_PAD_SHRINK && (pad_top >= kh || pad_bottom >= kh || pad_left >= kw || pad_right >= kw))
+        return SWS_ERR_INVALID_ARG;
+    if (mode == SWS_PAD_MIRROR && (pad_top > H - 1 || pad_bottom > H - 1 || pad_left > W - 1 || pad_right > W - 1))
+        return SWS_ERR_INVALID_ARG;
+    if (mode == SWS_PAD_PERIODIC && (pad_top > H || pad_bottom > H || pad_left > W || pad_right > W))
+        return SWS_ERR_INVALID_ARG;
+    const int64_t He = H + pad_top + pad_bottom, We = W + pad_left + pad_right;
+    if (He > kMaxDim || We > kMaxDim) return SWS_ERR_INVALID_ARG;
+    if (kh > He || kw > We) return SWS_ERR_INVALID_ARG;
+    const int64_t Ho = (He - kh) / sh + 1, Wo = (We - kw) / sw + 1;
+    int64_t planes, n_in, n_out;
+    if (!mul3(N, C, 1, &planes) || !mul3(planes, H, W, &n_in) || !mul3(planes, Ho, Wo, &n_out))
+        return SWS_ERR_INVALID_ARG;
+    if (He * We > kMaxDim) return SWS_ERR_UNSUPPORTED;
+    if (planes == 0) return SWS_OK;
+    if (!x || !y) return SWS_ERR_INVALID_ARG;
+    return SWS_LAUNCH(sws::launch_pool2d_padded((int)op, x, y, planes, H, W, Ho, Wo, kh, kw, sh, sw, pad_top, pad_left,
+                                               pad_bottom, pad_right, (int)mode, scale, (hipStream_t)stream));
+}
+
 sws_status sws_conv1d(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin, int64_t L,
                       int64_t Cout, int32_t k, int32_t stride, int32_t pad, int32_t dilation,
                       int32_t groups, sws_stream_t stream)

@@ -118,6 +118,10 @@ hipError_t launch_slide1d_generic(int op, const float *x, float *y, int64_t rows
 hipError_t launch_pool2d(int op, const float *x, float *y, int64_t planes, int64_t H, int64_t W,
                          int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
                          int32_t ph, int32_t pw, float scale, int div_valid, hipStream_t s);
+// Pooling over planes extended by a boundary rule on four sides (pool2d_padded.hip).
+hipError_t launch_pool2d_padded(int op, const float *x, float *y, int64_t planes, int64_t H, int64_t W, int64_t Ho,
+                                int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t pt, int32_t pl,
+                                int32_t pb, int32_t pr, int mode, float scale, hipStream_t s);
 hipError_t launch_maxpool2d_grad(const float *x, const float *gy, float *gx, int64_t planes, int64_t H, int64_t W,
                                  int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t ph,
                                  int32_t pw, hipStream_t s);

@@ -229,3 +229,19 @@ def test_headers_compile_as_plain_c(tmp_path):
                    'int f(sws_stream_t s) { return (int)sws_slide1d(SWS_OP_ADD, 0, 0, 0, 8, 3, 1.0f, s); }\n')
     subprocess.run([cc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-fsyntax-only",
                     "-I", os.path.join(ROOT, "include"), str(src)], check=True)
+
+
+def test_pool2d_padded_argument_checks(L):
+    one, nul = ctypes.c_void_p(16), ctypes.c_void_p(0)
+    i64, i32, f32 = ctypes.c_int64, ctypes.c_int32, ctypes.c_float
+    L.sws_pool2d_padded.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, i64, i64, i64, i64, i32, i32, i32, i32,
+                                    i32, i32, i32, i32, ctypes.c_int, f32, ctypes.c_void_p]
+    pp = lambda **kw: L.sws_pool2d_padded(*[kw.get(n, v) for n, v in zip(
+        ("op", "x", "y", "N", "C", "H", "W", "kh", "kw", "sh", "sw", "pt", "pl", "pb", "pr", "mode", "scale", "s"),
+        (0, one, one, 1, 3, 8, 6, 3, 3, 1, 1, 1, 0, 2, 1, 1, 1.0, nul))])
+    assert pp(N=0) == 0 and pp(C=0, mode=2) == 0
+    assert pp(mode=5) == 1 and pp(mode=-1) == 1 and pp(op=3) == 1 and pp(H=0) == 1 and pp(pr=-1) == 1
+    assert pp(pt=8) == 1 and pp(pb=8) == 1 and pp(pl=6) == 1 and pp(pr=6) == 1            # mirror: at most extent - 1
+    assert pp(mode=2, pt=9) == 1 and pp(mode=2, pr=7) == 1                                # periodic: at most the extent
+    assert pp(mode=4, pt=3) == 1 and pp(mode=4, pr=3) == 1                                # shrinking: below the window
+    assert pp(kh=12) == 1 and pp(kw=8) == 1 and pp(sh=0) == 1 and pp(x=nul) == 1 and pp(y=nul) == 1
