@@ -39,7 +39,9 @@ __global__ __launch_bounds__(kThreads) void pool2d_padded_kernel(const float *__
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
     if (unit >= n_units) return;
-    // in:  [rows_need][P]  the extended rows er0 .. of the band, columns ec0 .. ec0 + P - 1
+    // in:  [rows_need][P]  the extended rows er0 .. of the band; position q of a row holds extended column
+    //                      ec0 - lead + q, with lead in 0..3 chosen so that plane columns 4g .. 4g+3 sit on
+    //                      16-byte aligned positions
     // col: [nr][P]         those rows reduced down H
     const int ct = (int)(unit % ctiles);
     const int64_t pb = unit / ctiles;
@@ -51,25 +53,63 @@ __global__ __launch_bounds__(kThreads) void pool2d_padded_kernel(const float *__
     const int nr = (ho0 + TH < Ho ? ho0 + TH : Ho) - ho0;
     const int wo0 = ct * TWO;
     const int nwo = (wo0 + TWO < Wo ? wo0 + TWO : Wo) - wo0;
-    const int er0 = ho0 * sh, ec0 = wo0 * sw;        // first extended row and column staged
+    const int er0 = ho0 * sh, ec0 = wo0 * sw;        // first extended row and column the windows see
     const int rows_need = (nr - 1) * sh + kh;
+    const int lead = (((ec0 - pl) % 4) + 4) % 4;
+    const int shift = ec0 - pl - lead;               // plane column of position 0 (a multiple of 4)
+    const int used = lead + (nwo - 1) * sw + kw;     // positions the windows read
     float *in = lds_all + wave * lds_floats;
     float *col = in + ((TH - 1) * sh + kh) * P;
-    // ---- stage: eight loads per lane in flight; a row of the staged tile maps to one plane row, so a
-    //      wavefront's loads fall on runs of consecutive addresses except where a mirror turns them round
+    const v4f id4 = {O::id(), O::id(), O::id(), O::id()};
+    // ---- stage, part 1: the plane columns of the tile in whole groups of four — one 128-bit load and one
+    //      128-bit LDS write per group, the boundary rule applied to the row only
+    const int c_lo = ec0 - pl > 0 ? ec0 - pl : 0, c_hi = shift + used < W ? shift + used : W;
+    const int g_lo = (c_lo + 3) >> 2;
+    int g_hi = c_hi >> 2;
+    if (g_hi < g_lo) g_hi = g_lo;
+    const int ng = g_hi - g_lo;
+    if (ng > 0) {
+        const int n = rows_need * ng;
+        const float inv_ng = 1.0f / (float)ng;
+        constexpr int U = 4;
+        for (int i0 = 0; i0 < n; i0 += kWave * U) {
+            v4f v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + kWave * u + lane;
+                const int r = (int)(((float)i + 0.5f) * inv_ng), g = g_lo + i - r * ng;
+                const int sr = pad_src(er0 + r, H, pt, mode);
+                const bool ok = i < n && sr >= 0;
+                v[u] = *(const v4f_u *)(xp + (ok ? (int64_t)sr * W + 4 * g : 0));
+                v[u] = ok ? v[u] : id4;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + kWave * u + lane;
+                const int r = (int)(((float)i + 0.5f) * inv_ng), g = g_lo + i - r * ng;
+                if (i < n) *(v4f *)(in + r * P + 4 * g - shift) = v[u];
+            }
+        }
+    }
+    // ---- stage, part 2: the positions in front of and behind those groups (virtual columns, ragged ends),
+    //      one by one through the boundary rule of both axes
     {
-        const int n = rows_need * P;
-        const float inv_p = 1.0f / (float)P;
-        constexpr int U = 8;
+        const int q_front = ng > 0 ? 4 * g_lo - shift : P;   // positions 0 .. q_front - 1
+        const int q_back = ng > 0 ? 4 * g_hi - shift : P;    // positions q_back .. P - 1
+        const int nrem = q_front + P - q_back;
+        const int n = rows_need * nrem;
+        const float inv_n = 1.0f / (float)nrem;
+        constexpr int U = 4;
         for (int i0 = 0; i0 < n; i0 += kWave * U) {
             float v[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int i = i0 + kWave * u + lane;
-                const int r = (int)(((float)i + 0.5f) * inv_p), c = i - r * P;
-                const int ec = ec0 + c;
+                const int r = (int)(((float)i + 0.5f) * inv_n), e = i - r * nrem;
+                const int q = e < q_front ? e : e - q_front + q_back;
+                const int ec = ec0 - lead + q;
                 const int sr = pad_src(er0 + r, H, pt, mode);
-                const int sc = ec < We ? pad_src(ec, W, pl, mode) : -1;
+                const int sc = (q >= lead && ec < We) ? pad_src(ec, W, pl, mode) : -1;
                 const bool ok = i < n && sr >= 0 && sc >= 0;
                 v[u] = xp[ok ? (int64_t)sr * W + sc : 0];
                 v[u] = ok ? v[u] : O::id();
@@ -77,7 +117,9 @@ __global__ __launch_bounds__(kThreads) void pool2d_padded_kernel(const float *__
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int i = i0 + kWave * u + lane;
-                if (i < n) in[i] = v[u];
+                const int r = (int)(((float)i + 0.5f) * inv_n), e = i - r * nrem;
+                const int q = e < q_front ? e : e - q_front + q_back;
+                if (i < n) in[r * P + q] = v[u];
             }
         }
     }
@@ -108,7 +150,7 @@ __global__ __launch_bounds__(kThreads) void pool2d_padded_kernel(const float *__
     const float inv_wo = 1.0f / (float)nwo;
     for (int item = lane; item < nr * nwo; item += kWave) {
         const int r = (int)(((float)item + 0.5f) * inv_wo), wq = item - r * nwo;
-        const float *cr = col + r * P + wq * sw;
+        const float *cr = col + r * P + lead + wq * sw;
         float acc = cr[0];
         int b = 1;
         for (; b + 4 <= kw; b += 4) {
@@ -119,6 +161,135 @@ __global__ __launch_bounds__(kThreads) void pool2d_padded_kernel(const float *__
         if (OP == SWS_OP_ADD) acc *= scale;
         __builtin_nontemporal_store(acc, yp + (int64_t)(ho0 + r) * Wo + wo0 + wq);
     }
+}
+
+// ------------------------------------------------------------------------------------------------
+// The pooling layers' own shapes — 3 x 3 with one virtual column on the left (stride 1: and one on the
+// right), 2 x 2 stride 2 without virtual columns, rows of 4 .. 256 elements in multiples of 4 — without
+// LDS: a lane owns four adjacent columns, the W/4 lanes of a group hold one input row, the 64 / (W/4)
+// groups of a wavefront take consecutive bands of TH output rows.  A lane keeps the (TH-1)*S + K rows
+// of its band in registers (each read from the plane row the boundary rule names), forms the sum down
+// H on them, and takes the column beside its four from the neighbouring lane (DPP).  The rule acts on
+// rows and columns independently, so a virtual column of the row-reduced values is the reduced value
+// of the column it stands for: the second element of the same lane (mirror, left edge), its first
+// (repeated edge), or the last element of the group's last lane (periodic; one ds_bpermute) — and
+// likewise on the right.  A workgroup is one short-lived wavefront; XCD x takes planes 8q + x.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float lane_before(float v)       // the value held by lane - 1
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x138, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float lane_after(float v)        // the value held by lane + 1
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x130, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float from_lane(float v, int src)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(4 * src, __builtin_bit_cast(int, v)));
+}
+
+template <int OP, int K, int S, int PW, int TH>
+__global__ __launch_bounds__(kWave) void pool2d_padded_rows_kernel(const float *__restrict__ x, float *__restrict__ y,
+                                                                   int H, int W, int He, int Ho, int Wo, int pt, int mode,
+                                                                   int LPR, int G, int lpr_rcp, int64_t planes,
+                                                                   float scale)
+{
+    using O = Op<OP>;
+    constexpr int NL = PW;                                           // columns wanted from the lane before
+    constexpr int NRT = (S == 1) ? K - 1 - PW : (K - 2 - PW > 0 ? K - 2 - PW : 0);   // ... from the lane after
+    constexpr int NOUT = (S == 1) ? 4 : 2;                           // outputs per lane and row
+    constexpr int NR = (TH - 1) * S + K;                             // rows of a band
+    static_assert(NL <= 1 && NRT <= 1, "one virtual column on a side");
+    const int lane = threadIdx.x;
+    const int grp = (lane * lpr_rcp) >> 16, l = lane - grp * LPR;    // lane / LPR (exact for lane < 64)
+    if (grp >= G) return;
+    const int sl = (int)(blockIdx.x >> 3);
+    const int64_t plane = (int64_t)blockIdx.y * kXcd + (blockIdx.x & 7);
+    if (plane >= planes) return;
+    const int ho0 = (sl * G + grp) * TH;                             // first output row of my band
+    if (ho0 >= Ho) return;
+    const float *xp = x + plane * (int64_t)H * W + 4 * l;
+    float *yp = y + plane * (int64_t)Ho * Wo + NOUT * l;
+    v4f r[NR];
+#pragma unroll
+    for (int j = 0; j < NR; ++j) {                                   // all loads in flight together
+        const int er = ho0 * S + j;                                  // rows past the extended plane feed no stored output
+        const int row = er < He ? pad_src(er, H, pt, mode) : 0;
+        r[j] = *(const v4f_u *)(xp + (int64_t)row * W);
+    }
+    const bool first = l == 0, last = l == LPR - 1;
+#pragma unroll
+    for (int i = 0; i < TH; ++i) {
+        float e[NL + 4 + NRT];
+        v4f v = r[i * S];
+#pragma unroll
+        for (int a = 1; a < K; ++a) {
+            v.x = O::f(v.x, r[i * S + a].x); v.y = O::f(v.y, r[i * S + a].y);
+            v.z = O::f(v.z, r[i * S + a].z); v.w = O::f(v.w, r[i * S + a].w);
+        }
+        e[NL] = v.x; e[NL + 1] = v.y; e[NL + 2] = v.z; e[NL + 3] = v.w;
+        if constexpr (NL == 1) {
+            const float nb = lane_before(v.w);
+            float edge = mode == SWS_PAD_MIRROR ? v.y : v.x;
+            if (mode == SWS_PAD_PERIODIC) edge = from_lane(v.w, lane + LPR - 1);   // uniform branch: every lane takes part
+            e[0] = first ? edge : nb;
+        }
+        if constexpr (NRT == 1) {
+            const float nb = lane_after(v.x);
+            float edge = mode == SWS_PAD_MIRROR ? v.z : v.w;
+            if (mode == SWS_PAD_PERIODIC) edge = from_lane(v.x, lane - LPR + 1);
+            e[NL + 4] = last ? edge : nb;
+        }
+        float o[NOUT];
+#pragma unroll
+        for (int c = 0; c < NOUT; ++c) {
+            float acc = e[c * S];
+#pragma unroll
+            for (int b = 1; b < K; ++b) acc = O::f(acc, e[c * S + b]);
+            o[c] = (OP == SWS_OP_ADD) ? acc * scale : acc;
+        }
+        const int ho = ho0 + i;
+        if (ho < Ho) {
+            if constexpr (NOUT == 4) __builtin_nontemporal_store((v4f){o[0], o[1], o[2], o[3]}, (v4f_u *)(yp + (int64_t)ho * Wo));
+            else {
+                __builtin_nontemporal_store(o[0], yp + (int64_t)ho * Wo);
+                __builtin_nontemporal_store(o[1], yp + (int64_t)ho * Wo + 1);
+            }
+        }
+    }
+}
+
+template <int OP, int K, int S, int PW, int TH>
+hipError_t launch_padded_rows(const float *x, float *y, int64_t planes, int H, int W, int He, int Ho, int Wo, int pt,
+                              int mode, float scale, hipStream_t s, bool *taken)
+{
+    const int LPR = W / 4, G = kWave / LPR;
+    const int bands = (Ho + TH - 1) / TH;
+    const int spp = (bands + G - 1) / G;                             // wavefronts per plane
+    const int64_t rounds = (planes + kXcd - 1) / kXcd;
+    *taken = rounds <= 65535;
+    if (!*taken) return hipSuccess;
+    hipLaunchKernelGGL((pool2d_padded_rows_kernel<OP, K, S, PW, TH>), dim3((unsigned)(spp * kXcd), (unsigned)rounds),
+                       dim3(kWave), 0, s, x, y, H, W, He, Ho, Wo, pt, mode, LPR, G, (65536 + LPR - 1) / LPR, planes, scale);
+    return hipGetLastError();
+}
+
+// Band heights as for the kernel without boundary rules: two output rows per lane at stride 1, one at stride 2.
+template <int OP>
+hipError_t dispatch_padded_rows(const float *x, float *y, int64_t planes, int H, int W, int He, int Ho, int Wo, int kh,
+                                int kw, int sh, int sw, int pt, int pl, int pr, int mode, float scale, hipStream_t s,
+                                bool *taken)
+{
+    *taken = false;
+    if (kh != kw || sh != sw || (W & 3) || W < 4 || W > 256 || g_opt.pool2d_variant != 0) return hipSuccess;
+    if (mode != SWS_PAD_MIRROR && mode != SWS_PAD_PERIODIC && mode != SWS_PAD_EDGE) return hipSuccess;
+    if (kh == 3 && sh == 1 && pl == 1 && pr == 1)
+        return launch_padded_rows<OP, 3, 1, 1, 2>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
+    if (kh == 3 && sh == 2 && pl == 1 && Wo == W / 2)
+        return launch_padded_rows<OP, 3, 2, 1, 1>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
+    if (kh == 2 && sh == 2 && pl == 0 && Wo == W / 2)
+        return launch_padded_rows<OP, 2, 2, 0, 1>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
+    return hipSuccess;
 }
 
 // Direct evaluation for windows whose tile does not fit an LDS slice: one thread per output.
@@ -156,11 +327,15 @@ hipError_t launch_padded(const float *x, float *y, int64_t planes, int H, int W,
     // Tile sizing.  A slice holds (TH-1)*sh + kh staged rows and TH reduced rows of P floats.  Whole
     // rows of outputs where they fit; otherwise a few output rows per band, the widest pitch the slice
     // then allows (at least 16 outputs per tile) and as many outputs per tile as that pitch covers.
+    bool taken = false;
+    const hipError_t e = dispatch_padded_rows<OP>(x, y, planes, H, W, He, Ho, Wo, kh, kw, sh, sw, pt, pl, We - W - pl, mode,
+                                                  scale, s, &taken);
+    if (taken) return e;
     int P = 0, TH = 0, TWO = Wo, ctiles = 1, budget = 0;
     if (g_opt.pool2d_variant != 1) {
         for (const int bytes : {12 * 1024, 16 * 1024}) {
             budget = bytes / 4;
-            P = ((Wo - 1) * sw + kw + 3) / 4 * 4;
+            P = ((Wo - 1) * sw + kw + 3 + 3) / 4 * 4;   // up to three positions in front for alignment
             TWO = Wo;
             ctiles = 1;
             TH = (int)(((int64_t)budget / P - (kh - sh)) / (sh + 1));
@@ -168,11 +343,11 @@ hipError_t launch_padded(const float *x, float *y, int64_t planes, int H, int W,
             if (TH < 1 || (g_opt.pool2d_variant == 2 && Wo > 16)) {
                 for (TH = Ho < 4 ? Ho : 4; TH >= 1; --TH) {
                     P = budget / ((TH - 1) * sh + kh + TH) / 4 * 4;
-                    if (P >= kw + 15 * sw) break;
+                    if (P >= kw + 15 * sw + 3) break;
                 }
                 if (TH >= 1) {
-                    if (g_opt.pool2d_variant == 2) P = (kw + 15 * sw + 3) / 4 * 4;   // test knob: the narrowest tiles
-                    TWO = (P - kw) / sw + 1;
+                    if (g_opt.pool2d_variant == 2) P = (kw + 15 * sw + 3 + 3) / 4 * 4;   // test knob: the narrowest tiles
+                    TWO = (P - 3 - kw) / sw + 1;
                     if (TWO > Wo) TWO = Wo;
                     ctiles = (Wo + TWO - 1) / TWO;
                 }
@@ -195,7 +370,6 @@ hipError_t launch_padded(const float *x, float *y, int64_t planes, int H, int W,
             return hipGetLastError();
         }
     }
-    (void)He;
     int64_t grid = (n_out + kThreads - 1) / kThreads;
     const int64_t cap = (int64_t)device_cus() * 32;
     if (grid > cap) grid = cap;
