@@ -32,6 +32,7 @@ from .ref import (  # noqa: F401
     PAD_SHRINK,
     slide1d,
     pool2d_padded,
+    conv1d_padded,
     slide1d_padded,
     slide1d_pair,
     threads,

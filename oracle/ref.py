@@ -48,6 +48,9 @@ def _load():
         lib.sws_ref_pool2d_ex.restype = ctypes.c_int
         lib.sws_ref_pool2d_ex.argtypes = [ctypes.c_int, _fp, _dp, _dp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32,
                                           _i32, _i32, _i32, _i32, ctypes.c_int, _f64]
+        lib.sws_ref_conv1d_padded.restype = ctypes.c_int
+        lib.sws_ref_conv1d_padded.argtypes = [_fp, _fp, _dp, _dp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _i32,
+                                              ctypes.c_int]
         lib.sws_ref_pool2d_padded.restype = ctypes.c_int
         lib.sws_ref_pool2d_padded.argtypes = [ctypes.c_int, _fp, _dp, _dp, _i64, _i64, _i64, _i32, _i32, _i32, _i32,
                                               _i32, _i32, _i32, _i32, ctypes.c_int, _f64]
@@ -226,6 +229,27 @@ def conv1d(x, wgt, stride=1, pad=0, dilation=1, groups=1):
                                 k, stride, pad, dilation, groups)
     if rc:
         raise ValueError("sws_ref_conv1d rejected its arguments")
+    return y, s
+
+
+def conv1d_padded(x, wgt, stride=1, pad_left=0, pad_right=0, dilation=1, groups=1, mode=PAD_IDENTITY):
+    """x: [B, Cin, L], wgt: [Cout, Cin/groups, k] float32 -> (y, abs_sum) [B, Cout, Lo] float64: the convolution
+    over rows extended at both ends by the rule of `mode` (PAD_IDENTITY = zero padding)."""
+    x = _f32(x)
+    wgt = _f32(wgt)
+    b, cin, length = x.shape
+    cout, cig, k = wgt.shape
+    if cig * groups != cin:
+        raise ValueError("wgt.shape[1] * groups must equal Cin")
+    lo = (length + pad_left + pad_right - dilation * (k - 1) - 1) // stride + 1
+    if lo < 1:
+        raise ValueError("kernel longer than the extended row")
+    y = np.empty((b, cout, lo), np.float64)
+    s = np.empty((b, cout, lo), np.float64)
+    rc = _load().sws_ref_conv1d_padded(_ptr_f(x), _ptr_f(wgt), _ptr_d(y), _ptr_d(s), b, cin, length, cout, k, stride,
+                                       pad_left, pad_right, dilation, groups, mode)
+    if rc:
+        raise ValueError("sws_ref_conv1d_padded rejected its arguments")
     return y, s
 
 

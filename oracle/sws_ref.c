@@ -35,6 +35,8 @@
  *   sws_ref_pool2d_padded  the same boundary conditions in two dimensions: Eq. 3 over kh x kw
  *                    windows of planes extended on their four sides, both indices of every
  *                    window cell mapped back into the plane by the rule of the mode.
+ *   sws_ref_conv1d_padded  Eq. 4 per output over rows extended by the same boundary conditions:
+ *                    every tap's input index mapped back into the row (or dropped: zero padding).
  *   sws_ref_slide1d_pair  Eq. 3 with the pair operator of Section 2.4, Eq. 8:
  *                    (u_i, v_i) (+) (u_j, v_j) = (u_i*u_j, u_j*v_i + v_j), i older.
  *                    Non-commutative; folded strictly left to right.
@@ -673,6 +675,50 @@ int sws_ref_avgpool2d_grad(const float *gy, double *gx, double *abs_sum, int64_t
                         if (mp) mp[h * W + c] += fabs(term);
                     }
             }
+    }
+    return 0;
+}
+
+/* 1-D convolution (Section 2.5, Eq. 4 per output) over rows extended by pad_left elements in front and
+ * pad_right behind under a boundary condition of Section 3 (mode 0 zero padding, 1 mirror, 2 periodic,
+ * 3 edge replication):
+ *   y[b,co,i] = sum_ci sum_t wgt[co,ci,t] * xe[b, g*cig+ci, i*stride + t*dilation],  xe[e] = x[map(e - pad_left)]
+ * x: [B,Cin,L]; wgt: [Cout,Cin/groups,k]; y, abs_sum: [B,Cout,Lo], Lo = (L+pad_left+pad_right-span)/stride + 1. */
+int sws_ref_conv1d_padded(const float *x, const float *wgt, double *y, double *abs_sum, int64_t B, int64_t Cin,
+                          int64_t L, int64_t Cout, int32_t k, int32_t stride, int32_t pad_left, int32_t pad_right,
+                          int32_t dilation, int32_t groups, int mode)
+{
+    if (B < 0 || Cin < 1 || L < 1 || Cout < 1 || k < 1 || stride < 1 || pad_left < 0 || pad_right < 0 || dilation < 1 ||
+        groups < 1 || mode < 0 || mode > 3)
+        return 1;
+    if (Cin % groups || Cout % groups) return 1;
+    if (mode == 1 && (pad_left > L - 1 || pad_right > L - 1)) return 1;
+    if (mode == 2 && (pad_left > L || pad_right > L)) return 1;
+    const int64_t span = (int64_t)dilation * (k - 1) + 1, Le = L + pad_left + pad_right;
+    if (span > Le) return 1;
+    const int64_t Lo = (Le - span) / stride + 1;
+    const int64_t cig = Cin / groups, cog = Cout / groups;
+    if (B > 0 && (!x || !wgt || !y)) return 1;
+    const int64_t units = B * Cout;
+#pragma omp parallel for schedule(static)
+    for (int64_t u = 0; u < units; ++u) {
+        const int64_t b = u / Cout, co = u % Cout, g = co / cog;
+        for (int64_t i = 0; i < Lo; ++i) {
+            double acc = 0.0, mag = 0.0;
+            for (int64_t ci = 0; ci < cig; ++ci) {
+                const float *xr = x + (b * Cin + g * cig + ci) * L;
+                const float *wr = wgt + (co * cig + ci) * k;
+                for (int32_t t = 0; t < k; ++t) {
+                    const int64_t j = map_index(i * stride + (int64_t)t * dilation - pad_left, L, mode);
+                    if (j < 0) continue;                             /* zero padding */
+                    const double term = (double)wr[t] * (double)xr[j];
+                    acc += term;
+                    mag += fabs(term);
+                }
+            }
+            y[u * Lo + i] = acc;
+            if (abs_sum) abs_sum[u * Lo + i] = mag;
+        }
     }
     return 0;
 }

@@ -1058,3 +1058,61 @@ def test_pool2d_padded_reduces_to_the_other_pooling_functions_and_to_rows():
         oracle.pool2d_padded(OP_ADD, x, 3, 3, 1, 1, (12, 0, 0, 0), oracle.PAD_MIRROR)      # mirror reaches past the plane
     with pytest.raises(ValueError):
         oracle.pool2d_padded(OP_ADD, x, 3, 3, 1, 1, (0, 0, 0, 15), oracle.PAD_PERIODIC)
+
+
+# ----------------------------------------------------------------------------- P19
+# The convolution of Section 2.5 over rows extended by the boundary conditions of Section 3 (sws_ref_conv1d_padded).
+def test_conv1d_padded_hand_enumerated():
+    x = np.array([[[1, 2, 3, 4]]], np.float32)
+    taps = np.array([[[1, 10, 100]]], np.float32)
+    # extended rows, one element a side:  mirror 2 1 2 3 4 3 | periodic 4 1 2 3 4 1 | edge 1 1 2 3 4 4 | zero 0 1 2 3 4 0
+    want = {oracle.PAD_MIRROR: [212, 321, 432, 343], oracle.PAD_PERIODIC: [214, 321, 432, 143],
+            oracle.PAD_EDGE: [211, 321, 432, 443], oracle.PAD_IDENTITY: [210, 321, 432, 43]}
+    for mode, w in want.items():
+        y, m = oracle.conv1d_padded(x, taps, 1, 1, 1, 1, 1, mode)
+        assert y[0, 0].tolist() == w and m[0, 0].tolist() == w
+    # two in front, none behind, taps two apart, every second output: mirror row 3 2 1 2 3 4
+    y, _ = oracle.conv1d_padded(x, taps[:, :, :2], 2, 2, 0, 2, 1, oracle.PAD_MIRROR)
+    assert y[0, 0].tolist() == [3 + 10, 1 + 30]
+
+
+@pytest.mark.parametrize("mode,np_mode", [(1, "reflect"), (2, "wrap"), (3, "edge"), (0, "constant")])
+@pytest.mark.parametrize("geom", [(3, 1, 1, 1, 1, 1), (5, 2, 4, 0, 1, 1), (4, 1, 0, 7, 3, 1), (7, 3, 6, 6, 2, 2), (1, 1, 2, 3, 1, 4),
+                                  (9, 1, 8, 8, 1, 4)])
+def test_conv1d_padded_equals_convolution_of_an_explicitly_extended_row(mode, np_mode, geom):
+    k, stride, pl, pr, dil, groups = geom
+    r = _rng(190 + k + mode)
+    x = r.standard_normal((2, 4, 23), dtype=np.float32)
+    wgt = r.standard_normal((8, 4 // groups, k), dtype=np.float32)
+    ext = np.pad(x, ((0, 0), (0, 0), (pl, pr)), mode=np_mode)
+    y, m = oracle.conv1d_padded(x, wgt, stride, pl, pr, dil, groups, mode)
+    ref, mag = oracle.conv1d(ext, wgt, stride, 0, dil, groups)
+    assert np.array_equal(y, ref) and np.array_equal(m, mag)
+
+
+def test_conv1d_padded_periodic_is_circular_correlation_and_other_reductions():
+    r = _rng(191)
+    L, k = 64, 9
+    x = r.standard_normal((1, 1, L), dtype=np.float32)
+    taps = r.standard_normal((1, 1, k), dtype=np.float32)
+    y, _ = oracle.conv1d_padded(x, taps, 1, 0, k - 1, 1, 1, oracle.PAD_PERIODIC)
+    wl = np.zeros(L)
+    wl[:k] = taps[0, 0]
+    circ = np.fft.irfft(np.fft.rfft(x[0, 0].astype(np.float64)) * np.conj(np.fft.rfft(wl)), L)   # correlation theorem
+    assert y.shape == (1, 1, L) and np.allclose(y[0, 0], circ, atol=1e-12)
+    # zero padding, the same on both sides: the plain convolution
+    xs = r.standard_normal((2, 6, 40), dtype=np.float32)
+    ws = r.standard_normal((6, 2, 5), dtype=np.float32)
+    a, am = oracle.conv1d_padded(xs, ws, 2, 3, 3, 2, 3, oracle.PAD_IDENTITY)
+    b, bm = oracle.conv1d(xs, ws, 2, 3, 2, 3)
+    assert np.array_equal(a, b) and np.array_equal(am, bm)
+    # taps all one, one channel: the sliding sum over the padded row
+    ones = np.ones((1, 1, 7), np.float32)
+    for mode in range(4):
+        c, _ = oracle.conv1d_padded(xs[:1, :1], ones, 1, 3, 3, 1, 1, mode)
+        s, _ = oracle.slide1d_padded(OP_ADD, xs[0, :1], 7, 3, 3, mode)
+        assert np.allclose(c[0], s, atol=1e-12)
+    with pytest.raises(ValueError):
+        oracle.conv1d_padded(xs, ws, 1, 40, 0, 1, 3, oracle.PAD_MIRROR)
+    with pytest.raises(ValueError):
+        oracle.conv1d_padded(xs, ws, 1, 0, 41, 1, 3, oracle.PAD_PERIODIC)
