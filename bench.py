@@ -286,6 +286,16 @@ def sweeps_table(torch, B, workloads, iters=20):
             del y
     del u, v
     torch.cuda.empty_cache()
+    # configuration 5's depthwise layer with 15 mirrored elements at both ends of every row (sws_conv1d_padded)
+    x5, t5 = workloads.make(5)
+    x5, t5 = g(x5), g(t5)
+    y = torch.empty_like(x5)
+    ms = time_launches(torch, lambda: B.sws_conv1d_padded(x5, t5, 1, K5 // 2, K5 // 2, 1, CH5, B.SWS_PAD_MIRROR, y=y), iters)
+    nb = 8 * x5.numel()
+    out["same_size_pooling"]["dwconv_k31_mirror"] = {"ms": round(ms, 4), "GBps": round(nb / ms / 1e6, 1),
+                                                     "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+    del x5, y
+    torch.cuda.empty_cache()
     # the same in two dimensions: configuration 3's planes extended by k/2 mirrored rows and columns on every side
     x3 = g(workloads.make(3)[0])
     for op, opn in ((0, "avg"), (1, "max")):
@@ -527,6 +537,12 @@ def run_only(torch, B, workloads, name, steps, cold=False):
         taps = g(taps_host)
         y = torch.empty(256, 128, LEN5 - K5 + 1, device="cuda", dtype=torch.bfloat16)
         fn = lambda: B.sws_conv1d_16(x, taps, groups=CH5, y=y)
+    elif name.startswith("dwconv_k31_"):                  # dwconv_k31_<mirror|periodic|edge>: one output per input
+        mode = {"mirror": B.SWS_PAD_MIRROR, "periodic": B.SWS_PAD_PERIODIC, "edge": B.SWS_PAD_EDGE}[name.split("_")[2]]
+        x_host, taps_host = workloads.make(5)
+        x, taps = g(x_host), g(taps_host)
+        y = torch.empty(256, 128, LEN5, device="cuda")
+        fn = lambda: B.sws_conv1d_padded(x, taps, 1, K5 // 2, K5 // 2, 1, CH5, mode, y=y)
     elif name.startswith("slide_") or name == "dwconv_k31":
         x_host, taps_host = workloads.make(5)
         x = g(x_host)

@@ -239,6 +239,22 @@ sws_status sws_conv1d(const float *x, const float *wgt, float *y, int64_t B, int
                       int64_t L, int64_t Cout, int32_t k, int32_t stride, int32_t pad,
                       int32_t dilation, int32_t groups, sws_stream_t stream);
 
+/* sws_conv1d over rows extended by pad_left elements in front and pad_right behind under a boundary
+ * condition of Section 3 (the convolution of Section 2.5 with mirrored, periodic or edge-repeated
+ * ends instead of zeros; periodic with pad_right = k - 1 is the circular correlation):
+ *
+ *   y[b,co,i] = sum_{ci < Cin/groups} sum_{t < k} wgt[co,ci,t] * xe[b, g*Cin/groups + ci, i*stride + t*dilation]
+ *   xe[.., e] = x[.., src(e - pad_left)],  Lo = (L + pad_left + pad_right - dilation*(k-1) - 1)/stride + 1
+ *
+ * with src the index rule of `mode` as in sws_pad_mode (IDENTITY: the element is zero).
+ *   x : device [B,Cin,L]    wgt : device [Cout,Cin/groups,k]    y : device [B,Cout,Lo]
+ * Errors: as sws_conv1d; INVALID_ARG if L < 1, a pad is negative, the mode is unknown or
+ * SWS_PAD_SHRINK (a dot product has no shrinking form), a MIRROR pad exceeds L-1 or a PERIODIC pad
+ * exceeds L. */
+sws_status sws_conv1d_padded(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin, int64_t L,
+                             int64_t Cout, int32_t k, int32_t stride, int32_t pad_left, int32_t pad_right,
+                             int32_t dilation, int32_t groups, sws_pad_mode mode, sws_stream_t stream);
+
 /* sws_conv1d on 16-bit storage (the paper's introduction names quantisation as the way to shrink
  * what a layer moves; Section 2.5 itself is unchanged): x and y hold bf16 or fp16 elements, the taps
  * stay fp32.  Each element is widened to fp32 exactly, the sliding dot product is accumulated in

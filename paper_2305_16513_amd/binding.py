@@ -19,7 +19,7 @@ _lib = None
 
 _i64, _i32, _f32, _vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
 
-EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_maxpool2d_grad", "sws_avgpool2d_grad", "sws_pool2d_16", "sws_pool2d_ex", "sws_pool2d_padded", "sws_conv1d", "sws_conv1d_16", "sws_conv1d_grad_input", "sws_conv1d_grad_weight", "sws_conv2d", "sws_conv2d_grad_input", "sws_conv2d_grad_weight", "sws_copy", "sws_out_len",
+EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_maxpool2d_grad", "sws_avgpool2d_grad", "sws_pool2d_16", "sws_pool2d_ex", "sws_pool2d_padded", "sws_conv1d", "sws_conv1d_padded", "sws_conv1d_16", "sws_conv1d_grad_input", "sws_conv1d_grad_weight", "sws_conv2d", "sws_conv2d_grad_input", "sws_conv2d_grad_weight", "sws_copy", "sws_out_len",
            "sws_status_string", "sws_set_option", "sws_version")
 
 
@@ -64,6 +64,9 @@ def lib():
                                         _i32, _i32, _i32, _i32, ctypes.c_int, _f32, _vp]
         L.sws_conv1d.restype = ctypes.c_int
         L.sws_conv1d.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _vp]
+        L.sws_conv1d_padded.restype = ctypes.c_int
+        L.sws_conv1d_padded.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _i32,
+                                        ctypes.c_int, _vp]
         L.sws_conv1d_16.restype = ctypes.c_int
         L.sws_conv1d_16.argtypes = [ctypes.c_int, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _vp]
         for f in (L.sws_conv1d_grad_input, L.sws_conv1d_grad_weight):
@@ -298,6 +301,22 @@ def sws_pool2d_padded(op, x, kh, kw, sh=1, sw=1, pads=(0, 0, 0, 0), mode=0, scal
     y = _out(y, (n, c, ho, wo), x)
     _check(lib().sws_pool2d_padded(op, x.data_ptr(), y.data_ptr(), n, c, h, wd, kh, kw, sh, sw, pt, pl, pb, pr, mode,
                                    scale, _stream(stream)), "sws_pool2d_padded")
+    return y
+
+
+def sws_conv1d_padded(x, wgt, stride=1, pad_left=0, pad_right=0, dilation=1, groups=1, mode=0, y=None, stream=None):
+    """x [B, Cin, L], wgt [Cout, Cin/groups, k] -> y [B, Cout, Lo]: rows extended at both ends by the boundary
+    rule `mode` (SWS_PAD_IDENTITY = zeros, SWS_PAD_MIRROR, SWS_PAD_PERIODIC, SWS_PAD_EDGE)."""
+    _dev(x, "x")
+    _dev(wgt, "wgt")
+    b, cin, length = x.shape
+    cout, cig, k = wgt.shape
+    lo = (length + pad_left + pad_right - dilation * (k - 1) - 1) // stride + 1
+    if lo < 1 or cig * groups != cin or pad_left < 0 or pad_right < 0:
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_conv1d_padded")
+    y = _out(y, (b, cout, lo), x)
+    _check(lib().sws_conv1d_padded(x.data_ptr(), wgt.data_ptr(), y.data_ptr(), b, cin, length, cout, k, stride, pad_left,
+                                   pad_right, dilation, groups, mode, _stream(stream)), "sws_conv1d_padded")
     return y
 
 

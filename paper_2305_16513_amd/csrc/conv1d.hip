@@ -39,11 +39,13 @@ __device__ __forceinline__ void wave_lds_sync()
 // (lane l at 4*l) see one two-way conflict per eight lanes.
 __host__ __device__ constexpr int lds_pos(int q) { return q + 4 * (q >> 4); }
 
-template <int KB4>
+// RULE: the row is extended by `pad` elements in front and p_hi - L behind under the boundary rule
+// `pmode` (mirror, periodic, edge) instead of zeros; only the tiles at the ends of a row differ.
+template <int KB4, bool RULE>
 __global__ __launch_bounds__(kThreads, (KB4 <= 8 ? 5 : 4)) void conv1d_thin_kernel(
     const float *__restrict__ x, const float *__restrict__ wgt, float *__restrict__ y, int L, int Lo, int k,
     int pad, int Cin, int Cout, int cog, int tiles_per_row, int group, int chunks_per_row, int64_t n_units,
-    int wflip)
+    int wflip, int p_hi, int pmode)
 {
     constexpr int K4 = 4 * KB4;                      // taps, zero-padded to a multiple of 4
     constexpr int NI = kTileOut + K4;                // staged inputs per tile
@@ -95,6 +97,16 @@ __global__ __launch_bounds__(kThreads, (KB4 <= 8 ? 5 : 4)) void conv1d_thin_kern
                 const int p = s0 + 4 * lane;
                 if (s0 >= 0 && s0 + 256 <= L) {
                     g[j] = *(const v4f_u *)(xr + p);
+                } else if (RULE) {
+                    // virtual elements stand for the row element the rule names; beyond the extended row: zero
+                    float e4[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int q = p + u;
+                        const int src = (q >= -pad && q < p_hi) ? pad_src(q + pad, L, pad, pmode) : -1;
+                        e4[u] = src >= 0 ? xr[src] : 0.0f;
+                    }
+                    g[j] = (v4f){e4[0], e4[1], e4[2], e4[3]};
                 } else if (s0 >= L || s0 + 256 <= 0) {
                     g[j] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
                 } else {
@@ -165,9 +177,9 @@ __global__ __launch_bounds__(kThreads, (KB4 <= 8 ? 5 : 4)) void conv1d_thin_kern
     }
 }
 
-template <int KB4>
+template <int KB4, bool RULE = false>
 hipError_t launch_thin(const float *x, const float *wgt, float *y, int64_t rows_out, int L, int Lo, int k, int pad,
-                       int Cin, int Cout, int cog, hipStream_t s, int wflip)
+                       int Cin, int Cout, int cog, hipStream_t s, int wflip, int p_hi = 0, int pmode = 0)
 {
     const int tiles_per_row = (Lo + max_origin_shift(Lo, 16) + kTileOut - 1) / kTileOut;     // origins move back
     // Tiles per workgroup (measured): two per wavefront while HBM is the bound (the tiles in flight
@@ -180,8 +192,8 @@ hipError_t launch_thin(const float *x, const float *wgt, float *y, int64_t rows_
     const int64_t n_units = rows_out * chunks_per_row;
     const int64_t grid = xcd_grid(n_units);
     if (grid > 2147483647LL) return kNotTaken;
-    hipLaunchKernelGGL((conv1d_thin_kernel<KB4>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, wgt, y, L, Lo, k,
-                       pad, Cin, Cout, cog, tiles_per_row, group, chunks_per_row, n_units, wflip);
+    hipLaunchKernelGGL((conv1d_thin_kernel<KB4, RULE>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, wgt, y, L, Lo, k,
+                       pad, Cin, Cout, cog, tiles_per_row, group, chunks_per_row, n_units, wflip, p_hi, pmode);
     return hipGetLastError();
 }
 
@@ -628,6 +640,36 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
         return hipSuccess;
     }
     return launch_conv1d_naive(x, wgt, y, B, Cin, L, Cout, Lo, k, stride, pad, dilation, groups, s);
+}
+
+// Boundary rules other than zeros.  One input channel per output channel with adjacent taps at stride 1
+// (the paper's own 1-D case and the depthwise layers) runs on the sliding kernel, whose end tiles read
+// their virtual elements through the rule; zero padding, the same on both sides, is the plain entry
+// point's case; every other geometry is evaluated directly.
+hipError_t launch_conv1d_padded(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin, int64_t L,
+                                int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad_left, int32_t pad_right,
+                                int32_t dilation, int32_t groups, int mode, hipStream_t s)
+{
+    if (mode == SWS_PAD_IDENTITY && pad_left == pad_right)
+        return launch_conv1d(x, wgt, y, B, Cin, L, Cout, Lo, k, stride, pad_left, dilation, groups, s);
+    const int cig = (int)(Cin / groups), cog = (int)(Cout / groups);
+    if (cig == 1 && stride == 1 && dilation == 1 && k <= kThinMaxK && g_opt.conv1d_variant != 1) {
+        hipError_t e = kNotTaken;
+#define SWS_THIN_RULE(KB)                                                                                       \
+    case KB:                                                                                                    \
+        e = launch_thin<KB, true>(x, wgt, y, B * Cout, (int)L, (int)Lo, k, pad_left, (int)Cin, (int)Cout, cog, s, 0, \
+                                  (int)L + pad_right, mode);                                                    \
+        break
+        switch ((k + 3) / 4) {
+            SWS_THIN_RULE(1); SWS_THIN_RULE(2); SWS_THIN_RULE(3); SWS_THIN_RULE(4); SWS_THIN_RULE(5); SWS_THIN_RULE(6);
+            SWS_THIN_RULE(7); SWS_THIN_RULE(8); SWS_THIN_RULE(9); SWS_THIN_RULE(10); SWS_THIN_RULE(11); SWS_THIN_RULE(12);
+            SWS_THIN_RULE(13); SWS_THIN_RULE(14); SWS_THIN_RULE(15); SWS_THIN_RULE(16);
+        default: break;
+        }
+#undef SWS_THIN_RULE
+        if (e != kNotTaken) return e;
+    }
+    return launch_conv1d_naive(x, wgt, y, B, Cin, L, Cout, Lo, k, stride, pad_left, dilation, groups, s, mode);
 }
 
 }  // namespace sws

@@ -71,12 +71,13 @@ __global__ __launch_bounds__(kThreads) void pool2d_naive_kernel(const float *__r
     }
 }
 
-// Section 2.5: sliding dot product, taps applied in index order (no flip), zero padding.
+// Section 2.5: sliding dot product, taps applied in index order (no flip); the row is extended by `pad`
+// elements in front under the boundary rule `mode` (SWS_PAD_IDENTITY: zero padding).
 __global__ __launch_bounds__(kThreads) void conv1d_naive_kernel(const float *__restrict__ x,
                                                                 const float *__restrict__ wgt,
                                                                 float *__restrict__ y, int64_t B, int Cin,
                                                                 int L, int Cout, int Lo, int k, int stride,
-                                                                int pad, int dilation, int groups)
+                                                                int pad, int dilation, int groups, int mode)
 {
     const int cig = Cin / groups, cog = Cout / groups;
     const int64_t total = B * (int64_t)Cout * Lo;
@@ -91,8 +92,8 @@ __global__ __launch_bounds__(kThreads) void conv1d_naive_kernel(const float *__r
             const float *xr = x + (b * Cin + (int64_t)g * cig + ci) * L;
             const float *wr = wgt + ((int64_t)co * cig + ci) * k;
             for (int t = 0; t < k; ++t) {
-                const int64_t j = (int64_t)i * stride + (int64_t)t * dilation - pad;
-                if (j >= 0 && j < L) acc = fmaf(wr[t], xr[j], acc);
+                const int j = pad_src(i * stride + t * dilation, L, pad, mode);   // -1: zero padding
+                if (j >= 0) acc = fmaf(wr[t], xr[j], acc);
             }
         }
         y[o] = acc;
@@ -180,11 +181,11 @@ hipError_t launch_pool2d_naive(int op, const float *x, float *y, int64_t planes,
 
 hipError_t launch_conv1d_naive(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin,
                                int64_t L, int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad,
-                               int32_t dilation, int32_t groups, hipStream_t s)
+                               int32_t dilation, int32_t groups, hipStream_t s, int mode)
 {
     const int grid = grid_for(B * Cout * Lo);
     hipLaunchKernelGGL(conv1d_naive_kernel, dim3(grid), dim3(kThreads), 0, s, x, wgt, y, B, (int)Cin,
-                       (int)L, (int)Cout, (int)Lo, k, stride, pad, dilation, groups);
+                       (int)L, (int)Cout, (int)Lo, k, stride, pad, dilation, groups, mode);
     return hipGetLastError();
 }
 

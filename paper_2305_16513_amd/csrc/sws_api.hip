@@ -298,6 +298,30 @@ sws_status sws_conv1d(const float *x, const float *wgt, float *y, int64_t B, int
                                        (hipStream_t)stream));
 }
 
+sws_status sws_conv1d_padded(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin, int64_t L,
+                             int64_t Cout, int32_t k, int32_t stride, int32_t pad_left, int32_t pad_right,
+                             int32_t dilation, int32_t groups, sws_pad_mode mode, sws_stream_t stream)
+{
+    if (B < 0 || Cin < 1 || L < 1 || Cout < 1 || k < 1 || stride < 1 || pad_left < 0 || pad_right < 0 || dilation < 1 ||
+        groups < 1)
+        return SWS_ERR_INVALID_ARG;
+    if ((int)mode < SWS_PAD_IDENTITY || (int)mode > SWS_PAD_EDGE) return SWS_ERR_INVALID_ARG;
+    if (mode == SWS_PAD_MIRROR && (pad_left > L - 1 || pad_right > L - 1)) return SWS_ERR_INVALID_ARG;
+    if (mode == SWS_PAD_PERIODIC && (pad_left > L || pad_right > L)) return SWS_ERR_INVALID_ARG;
+    const int64_t Le = L + pad_left + pad_right;
+    if (Cin % groups || Cout % groups || Le > kMaxDim || Cin > kMaxDim || Cout > kMaxDim) return SWS_ERR_INVALID_ARG;
+    const int64_t span = (int64_t)dilation * (k - 1) + 1;
+    if (span > Le) return SWS_ERR_INVALID_ARG;
+    const int64_t Lo = (Le - span) / stride + 1;
+    int64_t n_in, n_out, n_w;
+    if (!mul3(B, Cin, L, &n_in) || !mul3(B, Cout, Lo, &n_out) || !mul3(Cout, Cin / groups, k, &n_w))
+        return SWS_ERR_INVALID_ARG;
+    if (B == 0) return SWS_OK;
+    if (!x || !wgt || !y) return SWS_ERR_INVALID_ARG;
+    return SWS_LAUNCH(sws::launch_conv1d_padded(x, wgt, y, B, Cin, L, Cout, Lo, k, stride, pad_left, pad_right, dilation,
+                                               groups, (int)mode, (hipStream_t)stream));
+}
+
 sws_status sws_conv1d_16(sws_dtype dtype, const void *x, const float *wgt, void *y, int64_t B, int64_t Cin, int64_t L,
                          int64_t Cout, int32_t k, int32_t stride, int32_t pad, int32_t dilation, int32_t groups,
                          sws_stream_t stream)

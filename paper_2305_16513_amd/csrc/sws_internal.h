@@ -139,6 +139,10 @@ hipError_t launch_pool2d_16(int op, int dtype, const void *x, void *y, int64_t p
 hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin, int64_t L,
                          int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad,
                          int32_t dilation, int32_t groups, hipStream_t s, int wadj = 0, bool *taken = nullptr);
+// Rows extended by pad_left / pad_right elements under a boundary rule (mirror, periodic, edge; conv1d.hip).
+hipError_t launch_conv1d_padded(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin, int64_t L,
+                                int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad_left, int32_t pad_right,
+                                int32_t dilation, int32_t groups, int mode, hipStream_t s);
 // 16-bit storage (conv1d16.hip): x, y bf16 / fp16, taps fp32.
 hipError_t launch_conv1d_16(int dtype, const void *x, const float *wgt, void *y, int64_t B, int64_t Cin, int64_t L,
                             int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad, int32_t dilation,
@@ -185,7 +189,7 @@ hipError_t launch_pool2d_naive(int op, const float *x, float *y, int64_t planes,
                                int32_t ph, int32_t pw, float scale, int div_valid, hipStream_t s);
 hipError_t launch_conv1d_naive(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin,
                                int64_t L, int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad,
-                               int32_t dilation, int32_t groups, hipStream_t s);
+                               int32_t dilation, int32_t groups, hipStream_t s, int mode = SWS_PAD_IDENTITY);
 hipError_t launch_conv2d_naive(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin,
                                int64_t H, int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh,
                                int32_t kw, int32_t sh, int32_t sw, int32_t ph, int32_t pw, hipStream_t s);

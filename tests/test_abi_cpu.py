@@ -245,3 +245,16 @@ def test_pool2d_padded_argument_checks(L):
     assert pp(mode=2, pt=9) == 1 and pp(mode=2, pr=7) == 1                                # periodic: at most the extent
     assert pp(mode=4, pt=3) == 1 and pp(mode=4, pr=3) == 1                                # shrinking: below the window
     assert pp(kh=12) == 1 and pp(kw=8) == 1 and pp(sh=0) == 1 and pp(x=nul) == 1 and pp(y=nul) == 1
+
+
+def test_conv1d_padded_argument_checks(L):
+    one, nul = ctypes.c_void_p(16), ctypes.c_void_p(0)
+    i64, i32 = ctypes.c_int64, ctypes.c_int32
+    L.sws_conv1d_padded.argtypes = [ctypes.c_void_p] * 3 + [i64] * 4 + [i32] * 6 + [ctypes.c_int, ctypes.c_void_p]
+    c = lambda **kw: L.sws_conv1d_padded(*[kw.get(n, v) for n, v in zip(
+        ("x", "w", "y", "B", "Cin", "L", "Cout", "k", "stride", "pl", "pr", "dil", "groups", "mode", "s"),
+        (one, one, one, 1, 4, 32, 4, 3, 1, 1, 1, 1, 4, 1, nul))])
+    assert c(B=0) == 0
+    assert c(mode=4) == 1 and c(mode=-1) == 1 and c(L=0) == 1 and c(pl=-1) == 1 and c(pr=-1) == 1
+    assert c(pl=32) == 1 and c(pr=32) == 1 and c(mode=2, pl=33) == 1 and c(mode=2, pr=33) == 1
+    assert c(groups=3) == 1 and c(k=0) == 1 and c(k=40) == 1 and c(stride=0) == 1 and c(dil=0) == 1 and c(y=nul) == 1
