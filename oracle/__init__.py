@@ -33,6 +33,7 @@ from .ref import (  # noqa: F401
     slide1d,
     pool2d_padded,
     conv1d_padded,
+    conv2d_padded,
     slide1d_padded,
     slide1d_pair,
     threads,

@@ -48,6 +48,9 @@ def _load():
         lib.sws_ref_pool2d_ex.restype = ctypes.c_int
         lib.sws_ref_pool2d_ex.argtypes = [ctypes.c_int, _fp, _dp, _dp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32,
                                           _i32, _i32, _i32, _i32, ctypes.c_int, _f64]
+        lib.sws_ref_conv2d_padded.restype = ctypes.c_int
+        lib.sws_ref_conv2d_padded.argtypes = [_fp, _fp, _dp, _dp, _i64, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32,
+                                              _i32, _i32, _i32, _i32, ctypes.c_int]
         lib.sws_ref_conv1d_padded.restype = ctypes.c_int
         lib.sws_ref_conv1d_padded.argtypes = [_fp, _fp, _dp, _dp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _i32,
                                               ctypes.c_int]
@@ -325,6 +328,28 @@ def pool2d_ex(op, x, kh, kw, sh=1, sw=1, pads=(0, 0, 0, 0), div_valid=False, sca
                                    1 if div_valid else 0, float(scale))
     if rc:
         raise ValueError("sws_ref_pool2d_ex rejected its arguments")
+    return y, s
+
+
+def conv2d_padded(x, wgt, sh=1, sw=1, pads=(0, 0, 0, 0), mode=PAD_IDENTITY):
+    """x: [N, Cin, H, W], wgt: [Cout, Cin, kh, kw] float32, pads = (top, left, bottom, right) ->
+    (y, abs_sum) [N, Cout, Ho, Wo] float64: planes extended on four sides by the rule of `mode`."""
+    x = _f32(x)
+    wgt = _f32(wgt)
+    n, cin, h, wd = x.shape
+    cout, cin2, kh, kw = wgt.shape
+    if cin2 != cin:
+        raise ValueError("wgt.shape[1] must equal Cin")
+    pt, pl, pb, pr = pads
+    ho, wo = (h + pt + pb - kh) // sh + 1, (wd + pl + pr - kw) // sw + 1
+    if ho < 1 or wo < 1:
+        raise ValueError("kernel larger than the extended plane")
+    y = np.empty((n, cout, ho, wo), np.float64)
+    s = np.empty((n, cout, ho, wo), np.float64)
+    rc = _load().sws_ref_conv2d_padded(_ptr_f(x), _ptr_f(wgt), _ptr_d(y), _ptr_d(s), n, cin, h, wd, cout, kh, kw, sh, sw,
+                                       pt, pl, pb, pr, mode)
+    if rc:
+        raise ValueError("sws_ref_conv2d_padded rejected its arguments")
     return y, s
 
 

@@ -37,6 +37,8 @@
  *                    window cell mapped back into the plane by the rule of the mode.
  *   sws_ref_conv1d_padded  Eq. 4 per output over rows extended by the same boundary conditions:
  *                    every tap's input index mapped back into the row (or dropped: zero padding).
+ *   sws_ref_conv2d_padded  the 2-D convolution over planes extended on four sides by those conditions,
+ *                    the row and the column index of every tap's input cell mapped independently.
  *   sws_ref_slide1d_pair  Eq. 3 with the pair operator of Section 2.4, Eq. 8:
  *                    (u_i, v_i) (+) (u_j, v_j) = (u_i*u_j, u_j*v_i + v_j), i older.
  *                    Non-commutative; folded strictly left to right.
@@ -718,6 +720,53 @@ int sws_ref_conv1d_padded(const float *x, const float *wgt, double *y, double *a
             }
             y[u * Lo + i] = acc;
             if (abs_sum) abs_sum[u * Lo + i] = mag;
+        }
+    }
+    return 0;
+}
+
+/* 2-D convolution (Section 2.5's sliding dot product on NCHW planes, OIHW taps, groups = 1) over planes
+ * extended on their four sides under a boundary condition of Section 3 (mode 0 zero padding, 1 mirror,
+ * 2 periodic, 3 edge replication); the rule maps the row index and the column index independently:
+ *   y[n,co,ho,wo] = sum_ci sum_a sum_b wgt[co,ci,a,b] * x[n,ci, map(ho*sh - pad_top + a), map(wo*sw - pad_left + b)]
+ * y, abs_sum: [N,Cout,Ho,Wo], Ho = (H+pad_top+pad_bottom-kh)/sh + 1, Wo likewise. */
+int sws_ref_conv2d_padded(const float *x, const float *wgt, double *y, double *abs_sum, int64_t N, int64_t Cin,
+                          int64_t H, int64_t W, int64_t Cout, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                          int32_t pad_top, int32_t pad_left, int32_t pad_bottom, int32_t pad_right, int mode)
+{
+    if (N < 0 || Cin < 1 || H < 1 || W < 1 || Cout < 1 || mode < 0 || mode > 3) return 1;
+    if (kh < 1 || kw < 1 || sh < 1 || sw < 1 || pad_top < 0 || pad_left < 0 || pad_bottom < 0 || pad_right < 0) return 1;
+    if (mode == 1 && (pad_top > H - 1 || pad_bottom > H - 1 || pad_left > W - 1 || pad_right > W - 1)) return 1;
+    if (mode == 2 && (pad_top > H || pad_bottom > H || pad_left > W || pad_right > W)) return 1;
+    const int64_t He = H + pad_top + pad_bottom, We = W + pad_left + pad_right;
+    if (kh > He || kw > We) return 1;
+    const int64_t Ho = (He - kh) / sh + 1, Wo = (We - kw) / sw + 1;
+    if (N > 0 && (!x || !wgt || !y)) return 1;
+    const int64_t units = N * Cout;
+#pragma omp parallel for schedule(static)
+    for (int64_t u = 0; u < units; ++u) {
+        const int64_t n = u / Cout, co = u % Cout;
+        for (int64_t ho = 0; ho < Ho; ++ho) {
+            for (int64_t wo = 0; wo < Wo; ++wo) {
+                double acc = 0.0, mag = 0.0;
+                for (int64_t ci = 0; ci < Cin; ++ci) {
+                    const float *xp = x + (n * Cin + ci) * H * W;
+                    const float *wp = wgt + (co * Cin + ci) * kh * kw;
+                    for (int32_t a = 0; a < kh; ++a) {
+                        const int64_t h = map_index(ho * sh - pad_top + a, H, mode);
+                        if (h < 0) continue;
+                        for (int32_t b = 0; b < kw; ++b) {
+                            const int64_t c = map_index(wo * sw - pad_left + b, W, mode);
+                            if (c < 0) continue;
+                            const double term = (double)wp[a * kw + b] * (double)xp[h * W + c];
+                            acc += term;
+                            mag += fabs(term);
+                        }
+                    }
+                }
+                y[(u * Ho + ho) * Wo + wo] = acc;
+                if (abs_sum) abs_sum[(u * Ho + ho) * Wo + wo] = mag;
+            }
         }
     }
     return 0;

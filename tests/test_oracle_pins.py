@@ -1116,3 +1116,69 @@ def test_conv1d_padded_periodic_is_circular_correlation_and_other_reductions():
         oracle.conv1d_padded(xs, ws, 1, 40, 0, 1, 3, oracle.PAD_MIRROR)
     with pytest.raises(ValueError):
         oracle.conv1d_padded(xs, ws, 1, 0, 41, 1, 3, oracle.PAD_PERIODIC)
+
+
+# ----------------------------------------------------------------------------- P20
+# The 2-D convolution over planes extended by the boundary conditions of Section 3 (sws_ref_conv2d_padded).
+def test_conv2d_padded_hand_enumerated():
+    x = np.array([[[[1, 2, 3], [4, 5, 6]]]], np.float32)
+    taps = np.array([[[[1, 10], [100, 1000]]]], np.float32)
+    # one row above, one column in front (the extended planes of test_pool2d_padded_hand_enumerated):
+    #   mirror 5 4 5 6 / 2 1 2 3 / 5 4 5 6   periodic 6 4 5 6 / 3 1 2 3 / 6 4 5 6   edge 1 1 2 3 / 1 1 2 3 / 4 4 5 6
+    want = {oracle.PAD_MIRROR: [[5 + 40 + 200 + 1000, 4 + 50 + 100 + 2000, 5 + 60 + 200 + 3000],
+                                [2 + 10 + 500 + 4000, 1 + 20 + 400 + 5000, 2 + 30 + 500 + 6000]],
+            oracle.PAD_PERIODIC: [[6 + 40 + 300 + 1000, 4 + 50 + 100 + 2000, 5 + 60 + 200 + 3000],
+                                  [3 + 10 + 600 + 4000, 1 + 20 + 400 + 5000, 2 + 30 + 500 + 6000]],
+            oracle.PAD_EDGE: [[1 + 10 + 100 + 1000, 1 + 20 + 100 + 2000, 2 + 30 + 200 + 3000],
+                              [1 + 10 + 400 + 4000, 1 + 20 + 400 + 5000, 2 + 30 + 500 + 6000]],
+            oracle.PAD_IDENTITY: [[1000, 100 + 2000, 200 + 3000], [10 + 4000, 1 + 20 + 400 + 5000, 2 + 30 + 500 + 6000]]}
+    for mode, w in want.items():
+        y, m = oracle.conv2d_padded(x, taps, 1, 1, (1, 1, 0, 0), mode)
+        assert y[0, 0].tolist() == w and m[0, 0].tolist() == w
+
+
+@pytest.mark.parametrize("mode,np_mode", [(1, "reflect"), (2, "wrap"), (3, "edge"), (0, "constant")])
+@pytest.mark.parametrize("geom", [(3, 3, 1, 1, (1, 1, 1, 1)), (2, 4, 2, 1, (0, 3, 1, 0)), (5, 1, 1, 2, (4, 0, 0, 0)),
+                                  (1, 6, 3, 3, (0, 2, 0, 5)), (7, 7, 1, 1, (6, 6, 6, 6))])
+def test_conv2d_padded_equals_convolution_of_an_explicitly_extended_plane(mode, np_mode, geom):
+    kh, kw, sh, sw, pads = geom
+    pt, pl, pb, pr = pads
+    r = _rng(200 + kh * 10 + kw + mode)
+    x = r.standard_normal((2, 3, 9, 11), dtype=np.float32)
+    wgt = r.standard_normal((4, 3, kh, kw), dtype=np.float32)
+    ext = np.pad(x, ((0, 0), (0, 0), (pt, pb), (pl, pr)), mode=np_mode)
+    y, m = oracle.conv2d_padded(x, wgt, sh, sw, pads, mode)
+    ref, mag = oracle.conv2d(ext, wgt, sh, sw, 0, 0)
+    assert np.array_equal(y, ref) and np.array_equal(m, mag)
+
+
+def test_conv2d_padded_periodic_is_circular_correlation_and_other_reductions():
+    r = _rng(201)
+    H, W, kh, kw = 12, 16, 3, 5
+    x = r.standard_normal((1, 1, H, W), dtype=np.float32)
+    taps = r.standard_normal((1, 1, kh, kw), dtype=np.float32)
+    y, _ = oracle.conv2d_padded(x, taps, 1, 1, (0, 0, kh - 1, kw - 1), oracle.PAD_PERIODIC)
+    wl = np.zeros((H, W))
+    wl[:kh, :kw] = taps[0, 0]
+    circ = np.fft.irfft2(np.fft.rfft2(x[0, 0].astype(np.float64)) * np.conj(np.fft.rfft2(wl)), (H, W))
+    assert y.shape == (1, 1, H, W) and np.allclose(y[0, 0], circ, atol=1e-12)
+    xs = r.standard_normal((2, 3, 10, 9), dtype=np.float32)
+    ws = r.standard_normal((5, 3, 3, 4), dtype=np.float32)
+    a, am = oracle.conv2d_padded(xs, ws, 2, 1, (1, 2, 1, 2), oracle.PAD_IDENTITY)
+    b, bm = oracle.conv2d(xs, ws, 2, 1, 1, 2)
+    assert np.array_equal(a, b) and np.array_equal(am, bm)
+    # one-row planes and taps: the 1-D convolution of the rows
+    for mode in range(4):
+        c, _ = oracle.conv2d_padded(xs[:, :, :1], ws[:, :, :1], 1, 2, (0, 3, 0, 1), mode)
+        d, _ = oracle.conv1d_padded(xs[:, :, 0], ws[:, :, 0], 2, 3, 1, 1, 1, mode)
+        assert np.array_equal(c[:, :, 0], d)
+    # all taps one, one channel: the pooling sum over the extended plane
+    ones = np.ones((1, 1, 3, 2), np.float32)
+    for mode in range(4):
+        c, _ = oracle.conv2d_padded(xs[:, :1], ones, 1, 1, (2, 1, 0, 1), mode)
+        p, _ = oracle.pool2d_padded(OP_ADD, xs[:, :1], 3, 2, 1, 1, (2, 1, 0, 1), mode)
+        assert np.allclose(c, p, atol=1e-12)
+    with pytest.raises(ValueError):
+        oracle.conv2d_padded(xs, ws, 1, 1, (10, 0, 0, 0), oracle.PAD_MIRROR)
+    with pytest.raises(ValueError):
+        oracle.conv2d_padded(xs, ws, 1, 1, (0, 0, 0, 10), oracle.PAD_PERIODIC)
