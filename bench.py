@@ -615,6 +615,12 @@ def run_only(torch, B, workloads, name, steps, cold=False):
         x4, w4 = g(x4), g(w4)
         y = torch.empty(32, 64, 56, 56, device="cuda")
         fn = rotating(x4, y)(lambda xx, yy: B.sws_conv2d(xx, w4, 1, 1, 1, 1, y=yy))
+    elif name.startswith("cfg4_conv2d_3x3_"):             # cfg4_conv2d_3x3_<mirror|periodic|edge>
+        mode = {"mirror": B.SWS_PAD_MIRROR, "periodic": B.SWS_PAD_PERIODIC, "edge": B.SWS_PAD_EDGE}[name.split("_")[3]]
+        x4, w4 = workloads.make(4)
+        x4, w4 = g(x4), g(w4)
+        y = torch.empty(32, 64, 56, 56, device="cuda")
+        fn = rotating(x4, y)(lambda xx, yy: B.sws_conv2d_padded(xx, w4, 1, 1, (1, 1, 1, 1), mode, y=yy))
     elif name == "cfg2_conv1d_64x64x3":
         x2, w2 = workloads.make(2)
         x2, w2 = g(x2), g(w2)

@@ -305,6 +305,25 @@ sws_status sws_conv2d(const float *x, const float *wgt, float *y, int64_t N, int
                       int64_t H, int64_t W, int64_t Cout, int32_t kh, int32_t kw,
                       int32_t sh, int32_t sw, int32_t ph, int32_t pw, sws_stream_t stream);
 
+/* sws_conv2d over planes extended on their four sides under a boundary condition of Section 3 (mirrored,
+ * periodic or edge-repeated borders instead of zeros; the rule maps the row index and the column index
+ * independently, as in sws_pool2d_padded):
+ *
+ *   y[n,co,ho,wo] = sum_ci sum_{a<kh} sum_{b<kw} wgt[co,ci,a,b] * xe[n,ci, ho*sh + a, wo*sw + b]
+ *   xe[n,ci,i,j]  = x[n,ci, src(i - pad_top, H), src(j - pad_left, W)]
+ *   Ho = (H + pad_top + pad_bottom - kh)/sh + 1,  Wo = (W + pad_left + pad_right - kw)/sw + 1
+ *
+ *   x : device [N,Cin,H,W]    wgt : device [Cout,Cin,kh,kw]    y : device [N,Cout,Ho,Wo]
+ * With equal pads on opposite sides the result is the zero-padding convolution (sws_conv2d's kernels
+ * and accuracy) plus the virtual cells' terms added to the outputs at the border in a second launch on
+ * the same stream; otherwise every output is evaluated directly.
+ * Errors: as sws_conv2d; INVALID_ARG if H or W < 1, a pad is negative, the mode is unknown or
+ * SWS_PAD_SHRINK, a MIRROR pad exceeds the extent of its axis minus 1 or a PERIODIC pad that extent. */
+sws_status sws_conv2d_padded(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
+                             int64_t W, int64_t Cout, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                             int32_t pad_top, int32_t pad_left, int32_t pad_bottom, int32_t pad_right,
+                             sws_pad_mode mode, sws_stream_t stream);
+
 /* The two adjoints of sws_conv2d, defined like those of sws_conv1d (loss = sum(gy * y)):
  *   gx[n,ci,h,c]     = sum over (co, a, b) with h + ph - a = ho*sh, c + pw - b = wo*sw inside the
  *                      output:  wgt[co,ci,a,b] * gy[n,co,ho,wo]

@@ -19,7 +19,7 @@ _lib = None
 
 _i64, _i32, _f32, _vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
 
-EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_maxpool2d_grad", "sws_avgpool2d_grad", "sws_pool2d_16", "sws_pool2d_ex", "sws_pool2d_padded", "sws_conv1d", "sws_conv1d_padded", "sws_conv1d_16", "sws_conv1d_grad_input", "sws_conv1d_grad_weight", "sws_conv2d", "sws_conv2d_grad_input", "sws_conv2d_grad_weight", "sws_copy", "sws_out_len",
+EXPORTS = ("sws_slide1d", "sws_slide1d_16", "sws_slide1d_padded", "sws_slide1d_pair", "sws_pool2d", "sws_maxpool2d_grad", "sws_avgpool2d_grad", "sws_pool2d_16", "sws_pool2d_ex", "sws_pool2d_padded", "sws_conv1d", "sws_conv1d_padded", "sws_conv1d_16", "sws_conv1d_grad_input", "sws_conv1d_grad_weight", "sws_conv2d", "sws_conv2d_padded", "sws_conv2d_grad_input", "sws_conv2d_grad_weight", "sws_copy", "sws_out_len",
            "sws_status_string", "sws_set_option", "sws_version")
 
 
@@ -64,6 +64,9 @@ def lib():
                                         _i32, _i32, _i32, _i32, ctypes.c_int, _f32, _vp]
         L.sws_conv1d.restype = ctypes.c_int
         L.sws_conv1d.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _vp]
+        L.sws_conv2d_padded.restype = ctypes.c_int
+        L.sws_conv2d_padded.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _i32, _i32,
+                                        _i32, ctypes.c_int, _vp]
         L.sws_conv1d_padded.restype = ctypes.c_int
         L.sws_conv1d_padded.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _i32, _i32, _i32, _i32,
                                         ctypes.c_int, _vp]
@@ -389,6 +392,23 @@ def sws_conv1d_grad_weight(x, gy, k, stride=1, pad=0, dilation=1, groups=1, gw=N
     _check(lib().sws_conv1d_grad_weight(x.data_ptr(), gy.data_ptr(), gw.data_ptr(), b, cin, length, cout, k, stride,
                                         pad, dilation, groups, _stream(stream)), "sws_conv1d_grad_weight")
     return gw
+
+
+def sws_conv2d_padded(x, wgt, sh=1, sw=1, pads=(0, 0, 0, 0), mode=0, y=None, stream=None):
+    """x [N, Cin, H, W], wgt [Cout, Cin, kh, kw], pads = (top, left, bottom, right) -> y [N, Cout, Ho, Wo]:
+    planes extended on four sides by the boundary rule `mode` (SWS_PAD_IDENTITY = zeros, MIRROR, PERIODIC, EDGE)."""
+    _dev(x, "x")
+    _dev(wgt, "wgt")
+    n, cin, h, wd = x.shape
+    cout, cin2, kh, kw = wgt.shape
+    pt, pl, pb, pr = pads
+    ho, wo = (h + pt + pb - kh) // sh + 1, (wd + pl + pr - kw) // sw + 1
+    if cin2 != cin or ho < 1 or wo < 1 or min(pads) < 0:
+        raise SwsError(SWS_ERR_INVALID_ARG, "sws_conv2d_padded")
+    y = _out(y, (n, cout, ho, wo), x)
+    _check(lib().sws_conv2d_padded(x.data_ptr(), wgt.data_ptr(), y.data_ptr(), n, cin, h, wd, cout, kh, kw, sh, sw,
+                                   pt, pl, pb, pr, mode, _stream(stream)), "sws_conv2d_padded")
+    return y
 
 
 def sws_conv2d(x, wgt, sh=1, sw=1, ph=0, pw=0, y=None, stream=None):

@@ -453,4 +453,32 @@ sws_status sws_conv2d(const float *x, const float *wgt, float *y, int64_t N, int
                                        (hipStream_t)stream));
 }
 
+sws_status sws_conv2d_padded(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
+                             int64_t W, int64_t Cout, int32_t kh, int32_t kw, int32_t sh, int32_t sw, int32_t pad_top,
+                             int32_t pad_left, int32_t pad_bottom, int32_t pad_right, sws_pad_mode mode,
+                             sws_stream_t stream)
+{
+    if (N < 0 || Cin < 1 || H < 1 || W < 1 || Cout < 1) return SWS_ERR_INVALID_ARG;
+    if (kh < 1 || kw < 1 || sh < 1 || sw < 1) return SWS_ERR_INVALID_ARG;
+    if (pad_top < 0 || pad_left < 0 || pad_bottom < 0 || pad_right < 0) return SWS_ERR_INVALID_ARG;
+    if ((int)mode < SWS_PAD_IDENTITY || (int)mode > SWS_PAD_EDGE) return SWS_ERR_INVALID_ARG;
+    if (mode == SWS_PAD_MIRROR && (pad_top > H - 1 || pad_bottom > H - 1 || pad_left > W - 1 || pad_right > W - 1))
+        return SWS_ERR_INVALID_ARG;
+    if (mode == SWS_PAD_PERIODIC && (pad_top > H || pad_bottom > H || pad_left > W || pad_right > W))
+        return SWS_ERR_INVALID_ARG;
+    const int64_t He = H + pad_top + pad_bottom, We = W + pad_left + pad_right;
+    if (He > kMaxDim || We > kMaxDim || Cin > kMaxDim || Cout > kMaxDim) return SWS_ERR_INVALID_ARG;
+    if (kh > He || kw > We) return SWS_ERR_INVALID_ARG;
+    const int64_t Ho = (He - kh) / sh + 1, Wo = (We - kw) / sw + 1;
+    int64_t t, n_in, n_out, n_w;
+    if (!mul3(N, Cin, H, &t) || !mul3(t, W, 1, &n_in)) return SWS_ERR_INVALID_ARG;
+    if (!mul3(N, Cout, Ho, &t) || !mul3(t, Wo, 1, &n_out)) return SWS_ERR_INVALID_ARG;
+    if (!mul3(Cout, Cin, (int64_t)kh * kw, &n_w)) return SWS_ERR_INVALID_ARG;
+    if (He * We > kMaxDim || n_w > kMaxDim) return SWS_ERR_UNSUPPORTED;
+    if (N == 0) return SWS_OK;
+    if (!x || !wgt || !y) return SWS_ERR_INVALID_ARG;
+    return SWS_LAUNCH(sws::launch_conv2d_padded(x, wgt, y, N, Cin, H, W, Cout, Ho, Wo, kh, kw, sh, sw, pad_top, pad_left,
+                                               pad_bottom, pad_right, (int)mode, (hipStream_t)stream));
+}
+
 }  // extern "C"

@@ -164,6 +164,11 @@ hipError_t launch_conv2d(const float *x, const float *wgt, float *y, int64_t N, 
                          int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw,
                          int32_t sh, int32_t sw, int32_t ph, int32_t pw, hipStream_t s);
 
+// Planes extended on four sides under a boundary rule (conv2d_padded.hip).
+hipError_t launch_conv2d_padded(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H, int64_t W,
+                                int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                                int32_t pt, int32_t pl, int32_t pb, int32_t pr, int mode, hipStream_t s);
+
 // Matrix-core convolution (conv_mfma.hip); *taken = false: shape not covered, nothing launched.
 hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
                               int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh,

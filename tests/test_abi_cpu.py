@@ -258,3 +258,16 @@ def test_conv1d_padded_argument_checks(L):
     assert c(mode=4) == 1 and c(mode=-1) == 1 and c(L=0) == 1 and c(pl=-1) == 1 and c(pr=-1) == 1
     assert c(pl=32) == 1 and c(pr=32) == 1 and c(mode=2, pl=33) == 1 and c(mode=2, pr=33) == 1
     assert c(groups=3) == 1 and c(k=0) == 1 and c(k=40) == 1 and c(stride=0) == 1 and c(dil=0) == 1 and c(y=nul) == 1
+
+
+def test_conv2d_padded_argument_checks(L):
+    one, nul = ctypes.c_void_p(16), ctypes.c_void_p(0)
+    i64, i32 = ctypes.c_int64, ctypes.c_int32
+    L.sws_conv2d_padded.argtypes = [ctypes.c_void_p] * 3 + [i64] * 5 + [i32] * 8 + [ctypes.c_int, ctypes.c_void_p]
+    c = lambda **kw: L.sws_conv2d_padded(*[kw.get(n, v) for n, v in zip(
+        ("x", "w", "y", "N", "Cin", "H", "W", "Cout", "kh", "kw", "sh", "sw", "pt", "pl", "pb", "pr", "mode", "s"),
+        (one, one, one, 1, 4, 8, 6, 6, 3, 3, 1, 1, 1, 1, 1, 1, 1, nul))])
+    assert c(N=0) == 0
+    assert c(mode=4) == 1 and c(mode=-1) == 1 and c(H=0) == 1 and c(pt=-1) == 1 and c(Cin=0) == 1
+    assert c(pt=8) == 1 and c(pr=6) == 1 and c(mode=2, pb=9) == 1 and c(mode=2, pl=7) == 1
+    assert c(kh=11) == 1 and c(kw=9) == 1 and c(sh=0) == 1 and c(y=nul) == 1 and c(w=nul) == 1
