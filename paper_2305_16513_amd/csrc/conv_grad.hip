@@ -641,6 +641,11 @@ hipError_t launch_conv2d_grad_weight(const float *x, const float *gy, float *gw,
         int64_t fg = (n_gw + kThreads - 1) / kThreads;
         if (fg > 4096) fg = 4096;
         hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)fg), dim3(kThreads), 0, s, gw, n_gw);
+        {
+            bool taken_s = false;
+            const hipError_t es = launch_conv2d_gw_split(x, gy, gw, N, Cin, H, W, Cout, Ho, Wo, kh, kw, sh, sw, ph, pw, s, &taken_s);
+            if (taken_s || es != hipSuccess) return es;
+        }
         GwGeom gm;
         gm.Cin = (int)Cin; gm.Cout = (int)Cout; gm.L = (int)W; gm.Lo = (int)Wo; gm.k = kw; gm.pad = pw; gm.dilation = 1;
         gm.H = (int)H; gm.Ho = (int)Ho; gm.kh = kh; gm.sh = sh; gm.ph = ph; gm.sw = sw; gm.x_cs = H * W; gm.gy_cs = Ho * Wo;

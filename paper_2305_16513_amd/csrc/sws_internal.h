@@ -169,6 +169,12 @@ hipError_t launch_conv2d_padded(const float *x, const float *wgt, float *y, int6
                                 int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
                                 int32_t pt, int32_t pl, int32_t pb, int32_t pr, int mode, hipStream_t s);
 
+// Dense grad-weight on the bf16 matrix cores with split fp32 operands (conv_gw_split.hip): 3 x 3, horizontal
+// stride 1, channel counts in multiples of 32; gw must hold zeros; *taken = false: not its case, nothing launched.
+hipError_t launch_conv2d_gw_split(const float *x, const float *gy, float *gw, int64_t N, int64_t Cin, int64_t H, int64_t W,
+                                  int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                                  int32_t ph, int32_t pw, hipStream_t s, bool *taken);
+
 // Matrix-core convolution (conv_mfma.hip); *taken = false: shape not covered, nothing launched.
 hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
                               int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh,

@@ -327,3 +327,46 @@ def test_conv2d_grad_input_on_the_streaming_kernels(B, case, variant):
     assert_within_tol(gx, rx, mx, "streaming grad_input %s variant %d" % (case, variant))
     rxi, _ = oracle.conv2d_grad_input(gi, wi, h, wd, sh, sw, ph, pw)
     assert np.array_equal(gxi.astype(np.float64), rxi), "streaming grad_input, integers %s variant %d" % (case, variant)
+
+
+# 3 x 3, horizontal stride 1, channel counts in multiples of 32: the grad-weight kernel on the bf16 matrix cores
+# with split fp32 operands.  Rows that are not whole groups of 8 positions, blocks of 64 x 64 channels with an idle
+# half, vertical strides, no padding, images whose groups split unevenly over the workgroups.
+SPLIT_GW = [(2, 32, 20, 20, 32, 3, 3, 1, 1, 1, 1), (3, 96, 13, 13, 32, 3, 3, 1, 1, 1, 1), (1, 32, 9, 7, 160, 3, 3, 1, 1, 1, 1),
+            (5, 64, 11, 30, 64, 3, 3, 2, 1, 1, 1), (2, 128, 10, 19, 64, 3, 3, 1, 1, 0, 0), (7, 32, 3, 3, 32, 3, 3, 1, 1, 1, 1),
+            (2, 64, 17, 9, 96, 3, 3, 3, 1, 0, 2), (1, 32, 3, 5, 32, 3, 3, 1, 1, 0, 0)]
+
+
+@pytest.mark.parametrize("integer", [False, True])
+@pytest.mark.parametrize("case", SPLIT_GW)
+def test_split_operand_grad_weight(B, case, integer):
+    n, cin, h, wd, cout, kh, kw, sh, sw, ph, pw = case
+    x, _, g = _data2d(case, 500 + cin + wd, integer)
+    gw = to_host(B.sws_conv2d_grad_weight(to_gpu(x), to_gpu(g), kh, kw, sh, sw, ph, pw))
+    rw, mw = oracle.conv2d_grad_weight(x, g, kh, kw, sh, sw, ph, pw)
+    if integer:
+        assert np.array_equal(gw.astype(np.float64), rw), str(case)
+    else:
+        worst = assert_within_tol(gw, rw, mw, "split grad_weight %s" % (case,))
+        assert worst < 2e-6, (case, worst)                       # fp32 accuracy, not bf16's
+    B.sws_set_option("conv2d_variant", 3)                        # the fp32-instruction kernel
+    try:
+        other = to_host(B.sws_conv2d_grad_weight(to_gpu(x), to_gpu(g), kh, kw, sh, sw, ph, pw))
+    finally:
+        B.sws_set_option("conv2d_variant", 0)
+    if integer:
+        assert np.array_equal(gw, other), str(case)
+    else:
+        assert_within_tol(other, rw, mw, "fp32-instruction grad_weight %s" % (case,))
+
+
+def test_split_operand_grad_weight_carries_every_bit(B):
+    """Inputs whose low mantissa bits matter: x = 1 + k * 2^-23 against gradients of +-1 that cancel the ones —
+    what is left lives entirely in the third bf16 piece."""
+    r = np.random.Generator(np.random.PCG64(61))
+    kx = r.integers(0, 128, size=(2, 32, 10, 16))
+    x = (1.0 + kx * 2.0 ** -23).astype(np.float32)
+    g = np.where(r.integers(0, 2, size=(2, 32, 10, 16)) > 0, 1.0, -1.0).astype(np.float32)
+    gw = to_host(B.sws_conv2d_grad_weight(to_gpu(x), to_gpu(g), 3, 3, 1, 1, 1, 1))
+    rw, mw = oracle.conv2d_grad_weight(x, g, 3, 3, 1, 1, 1, 1)
+    assert_within_tol(gw, rw, mw, "low bits", tol=2e-7)
