@@ -1,8 +1,8 @@
 // The adjoint of the dense 2-D convolution with respect to its weights (the training side of
 // Section 2.5's sliding dot product), horizontal stride 1, on the bf16 matrix cores with exactly split
-// fp32 operands:
+// fp32 operands (stride 1):
 //
-//   gw[co][ci][a][b] = sum over (n, ho, wo) of  gy[n][co][ho][wo] * x[n][ci][ho*sh - ph + a][wo - pw + b]
+//   gw[co][ci][a][b] = sum over (n, ho, wo) of  gy[n][co][ho][wo] * x[n][ci][ho - ph + a][wo - pw + b]
 //
 // is, for each tap (a, b), a matrix product GY[co][positions] * X_ab[positions][ci] whose contraction
 // index — the position — is also the index that is contiguous in memory for both operands.  The
@@ -15,9 +15,10 @@
 // the term — so the result has fp32 accuracy at 6/16 of the fp32 matrix instruction's time.
 //
 // A workgroup owns a 64 x 64 block of (co, ci) — one 32 x 32 block and all KH*KW taps per wavefront,
-// 16 accumulator registers per tap — and a contiguous share of the positions, walked in groups of 8 along
-// the output rows (the two halves of a wavefront take consecutive groups, which need not lie in the
-// same row).  At the end the blocks go through LDS, 16 output channels at a time, and leave as atomic
+// 16 accumulator registers per tap — and a share of the positions, cut into tasks of a column of 8
+// positions by S output rows (the two halves of a wavefront take two tasks).  Walking down a column, a step
+// converts (splits, packs) one new input row and keeps the two it shares with the step before; that
+// conversion runs in the shadow of the matrix instructions, and loads run two steps ahead of it.  At the end the blocks go through LDS, 16 output channels at a time, and leave as atomic
 // adds whose lanes run over contiguous (ci, tap) — adds to one cache line serialise, so as few
 // instructions as possible touch each line.  gw is cleared by the caller first; the order of the adds
 // is not fixed.
@@ -44,16 +45,26 @@ __device__ __forceinline__ void split3(float v, float &p2, float &p3)
     p3 = p2 - __uint_as_float(__float_as_uint(p2) & 0xffff0000u);
 }
 
-template <int KH, int KW>
+// One kernel row's inputs of a lane as matrix operands: for each of the KW taps the 8 positions it meets,
+// in three bf16 pieces.
+template <int KW> struct RowOperand {
+    v8bf b[KW][3];
+};
+
+template <int KH, int KW, int PW>
 __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *__restrict__ x, const float *__restrict__ gy,
                                                                    float *__restrict__ gw, int Cin, int H, int W, int Cout,
-                                                                   int Ho, int Wo, int sh, int ph, int pw, int g8,
-                                                                   int64_t n_groups, int64_t groups_per_wg, int ci_blocks,
-                                                                   int64_t x_total)
+                                                                   int Ho, int Wo, int ph, int g8, int S, int nseg,
+                                                                   int64_t n_tasks, int64_t pairs_per_wg, int ci_blocks,
+                                                                   int64_t x_total, int64_t gy_total)
 {
+    static_assert(KH == 3, "the ring of kernel rows below is written for three");
     constexpr int T = KH * KW;
     constexpr int NV = 8 + KW - 1;                   // inputs a lane needs per kernel row
-    constexpr int NCH = (NV + 3) / 4;                // ... in 128-bit loads
+    // W and Wo are multiples of 4 and a column starts at a multiple of 8, so the first input a lane needs sits
+    // D elements into a 16-byte group of the tensor: loads of whole groups never straddle an end of the tensor
+    constexpr int D = (4 - PW % 4) % 4;
+    constexpr int NCH = (D + NV + 3) / 4;            // groups per kernel row
     __shared__ float red[16][64 * T + 1];
     const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -67,89 +78,52 @@ __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
 
-    const int64_t G0 = blockIdx.x * groups_per_wg;
-    const int64_t G1 = G0 + groups_per_wg < n_groups ? G0 + groups_per_wg : n_groups;
+    // A task: S consecutive output rows of one column of 8 positions of one image.  Walking down the column,
+    // the input rows of consecutive steps overlap: a step converts one new input row and keeps two.
+    const int64_t P0 = blockIdx.x * pairs_per_wg;
+    const int64_t P1 = P0 + pairs_per_wg < (n_tasks + 1) / 2 ? P0 + pairs_per_wg : (n_tasks + 1) / 2;
     if (active) {
-        // my first group of 8 positions: output row (n, ho), group gi of the row; then two groups further per step
-        int64_t n;
-        int ho, gi;
-        {
-            const int64_t mg0 = G0 + half, row0 = mg0 / g8;
-            gi = (int)(mg0 - row0 * g8);
-            n = row0 / Ho;
-            ho = (int)(row0 - n * Ho);
-        }
-        for (int64_t G = G0; G < G1; G += 2) {
-            const bool valid = G + half < G1;
-            const int64_t nn = valid ? n : 0;                    // a lane without a group points at the first row
-            const int hh = valid ? ho : 0;
-            const int wo0 = valid ? gi * 8 : 0;
-            // ---- gradients: 8 consecutive positions of my output channel
-            float ga[8];
-            {
-                const float *gp = gy + ((nn * Cout + co) * Ho + hh) * (int64_t)Wo + wo0;
-                const bool fast = valid && wo0 + 8 <= Wo;
-                if (__builtin_amdgcn_ballot_w64(valid && !fast) == 0) {
-                    const v4f a0 = *(const v4f_u *)(fast ? gp : gy), a1 = *(const v4f_u *)(fast ? gp + 4 : gy);
-                    ga[0] = a0.x; ga[1] = a0.y; ga[2] = a0.z; ga[3] = a0.w; ga[4] = a1.x; ga[5] = a1.y; ga[6] = a1.z; ga[7] = a1.w;
+        for (int64_t P = P0; P < P1; ++P) {
+            const int64_t task = 2 * P + half;
+            const bool tv = task < n_tasks;
+            const int64_t col = tv ? task / nseg : 0;
+            const int seg = tv ? (int)(task - col * nseg) : 0;
+            const int64_t n = col / g8;
+            const int wo0 = (int)(col - n * g8) * 8, h0 = seg * S;
+            const float *xp = x + (n * Cin + ci) * (int64_t)H * W;       // my input plane
+            const float *gp = gy + (n * Cout + co) * (int64_t)Ho * Wo;   // my gradient plane
+            const int p0 = wo0 - PW;
+            const int64_t x_groups = x_total >> 2, gy_groups = gy_total >> 2;
+            // the groups that hold positions p0 .. p0 + NV - 1 of input row r, as loaded (no branches, nothing
+            // waits here): groups beyond an end of the tensor are taken from its first / last group, and every
+            // cell outside the plane is zeroed at conversion time (position < wlim)
+            auto load_row = [&](int r, float (&xv)[4 * NCH], unsigned &wlim) {
+                const bool rowok = tv && r >= 0 && r < H;
+                wlim = rowok ? (unsigned)W : 0u;
+                const int64_t g0 = ((xp - x) + (int64_t)(rowok ? r : 0) * W + (p0 - D)) >> 2;    // may be -1
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) ga[e] = fast ? ga[e] : 0.0f;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const bool ok = valid && wo0 + e < Wo;
-                        const float t = gp[ok ? e : 0];
-                        ga[e] = ok ? t : 0.0f;
-                    }
-                }
-            }
-            unsigned A[3][4];
-            {
-                float p2[8], p3[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) split3(ga[e], p2[e], p3[e]);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    A[0][i] = pack_hi(ga[2 * i], ga[2 * i + 1]);
-                    A[1][i] = pack_hi(p2[2 * i], p2[2 * i + 1]);
-                    A[2][i] = pack_hi(p3[2 * i], p3[2 * i + 1]);
-                }
-            }
-            const v8bf a1 = __builtin_bit_cast(v8bf, (v4u){A[0][0], A[0][1], A[0][2], A[0][3]});
-            const v8bf a2 = __builtin_bit_cast(v8bf, (v4u){A[1][0], A[1][1], A[1][2], A[1][3]});
-            const v8bf a3 = __builtin_bit_cast(v8bf, (v4u){A[2][0], A[2][1], A[2][2], A[2][3]});
-#pragma unroll
-            for (int a = 0; a < KH; ++a) {
-                // ---- inputs: positions wo0 - pw .. wo0 - pw + NV - 1 of row ho*sh - ph + a of my input channel
-                const int r = hh * sh - ph + a;
-                const bool rowok = valid && r >= 0 && r < H;
-                const int p0 = wo0 - pw;
-                const float *xr = x + ((nn * Cin + ci) * H + (rowok ? r : 0)) * (int64_t)W;
-                float xv[4 * NCH];
-                // the 128-bit loads may run over the ends of the row (into the neighbouring rows: masked below);
-                // only at the two ends of the whole tensor must they not
-                const int64_t at = (xr - x) + p0;
-                const bool fast = rowok && at >= 0 && at + 4 * NCH <= x_total;
-                if (__builtin_amdgcn_ballot_w64(rowok && !fast) == 0) {
-#pragma unroll
-                    for (int j = 0; j < NCH; ++j) {
-                        const v4f q = *(const v4f_u *)(fast ? xr + p0 + 4 * j : x);
-                        const float qe[4] = {q.x, q.y, q.z, q.w};
+                for (int j = 0; j < NCH; ++j) {
+                    int64_t g = g0 + j;
+                    g = g < 0 ? 0 : (g >= x_groups ? x_groups - 1 : g);
+                    // only what is used is loaded: a register of a load still in flight that nothing reads would be
+                    // handed out again, and writing it waits for the load
+                    if (4 * j >= D && 4 * j + 4 <= D + NV) {
+                        const v4f q = *(const v4f_u *)(x + 4 * g);
+                        xv[4 * j] = q.x; xv[4 * j + 1] = q.y; xv[4 * j + 2] = q.z; xv[4 * j + 3] = q.w;
+                    } else {
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            xv[4 * j + e] = (fast && p0 + 4 * j + e >= 0 && p0 + 4 * j + e < W) ? qe[e] : 0.0f;
-                    }
-                } else {
-#pragma unroll
-                    for (int e = 0; e < NV; ++e) {
-                        const bool ok = rowok && p0 + e >= 0 && p0 + e < W;
-                        const float t = xr[ok ? p0 + e : 0];
-                        xv[e] = ok ? t : 0.0f;
+                            if (4 * j + e >= D && 4 * j + e < D + NV) xv[4 * j + e] = x[4 * g + e];
                     }
                 }
-                float q2[NV], q3[NV];
+            };
+            auto convert_row = [&](const float (&raw)[4 * NCH], unsigned wlim, RowOperand<KW> &R) {
+                float xv[NV], q2[NV], q3[NV];
 #pragma unroll
-                for (int e = 0; e < NV; ++e) split3(xv[e], q2[e], q3[e]);
+                for (int e = 0; e < NV; ++e) {
+                    xv[e] = (unsigned)(p0 + e) < wlim ? raw[D + e] : 0.0f;
+                    split3(xv[e], q2[e], q3[e]);
+                }
 #pragma unroll
                 for (int b = 0; b < KW; ++b) {
                     unsigned Bp[3][4];
@@ -159,23 +133,87 @@ __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *
                         Bp[1][i] = pack_hi(q2[b + 2 * i], q2[b + 2 * i + 1]);
                         Bp[2][i] = pack_hi(q3[b + 2 * i], q3[b + 2 * i + 1]);
                     }
-                    const v8bf b1 = __builtin_bit_cast(v8bf, (v4u){Bp[0][0], Bp[0][1], Bp[0][2], Bp[0][3]});
-                    const v8bf b2 = __builtin_bit_cast(v8bf, (v4u){Bp[1][0], Bp[1][1], Bp[1][2], Bp[1][3]});
-                    const v8bf b3 = __builtin_bit_cast(v8bf, (v4u){Bp[2][0], Bp[2][1], Bp[2][2], Bp[2][3]});
+#pragma unroll
+                    for (int pc = 0; pc < 3; ++pc)
+                        R.b[b][pc] = __builtin_bit_cast(v8bf, (v4u){Bp[pc][0], Bp[pc][1], Bp[pc][2], Bp[pc][3]});
+                }
+            };
+            // 8 consecutive gradients of output row ho, as loaded; glim = how many of them count (none beyond the
+            // segment or the plane)
+            auto load_grad = [&](int ho, int i, float (&ga)[8], unsigned &glim) {
+                const bool ok_row = tv && i < S && ho < Ho;
+                glim = ok_row ? (unsigned)(Wo - wo0) : 0u;
+                const int64_t g0 = ((gp - gy) + (int64_t)(ok_row ? ho : 0) * Wo + wo0) >> 2;
+                const int64_t g1 = g0 + 1 < gy_groups ? g0 + 1 : gy_groups - 1;
+                const v4f a0 = *(const v4f_u *)(gy + 4 * g0), a1 = *(const v4f_u *)(gy + 4 * g1);
+                ga[0] = a0.x; ga[1] = a0.y; ga[2] = a0.z; ga[3] = a0.w; ga[4] = a1.x; ga[5] = a1.y; ga[6] = a1.z; ga[7] = a1.w;
+            };
+            struct GradOperand { v8bf a[3]; };
+            auto convert_grad = [&](const float (&raw)[8], unsigned glim, GradOperand &A) {
+                float ga[8], p2[8], p3[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    ga[e] = (unsigned)e < glim ? raw[e] : 0.0f;
+                    split3(ga[e], p2[e], p3[e]);
+                }
+                unsigned w[3][4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    w[0][k] = pack_hi(ga[2 * k], ga[2 * k + 1]);
+                    w[1][k] = pack_hi(p2[2 * k], p2[2 * k + 1]);
+                    w[2][k] = pack_hi(p3[2 * k], p3[2 * k + 1]);
+                }
+#pragma unroll
+                for (int pc = 0; pc < 3; ++pc) A.a[pc] = __builtin_bit_cast(v8bf, (v4u){w[pc][0], w[pc][1], w[pc][2], w[pc][3]});
+            };
+            // Step i (output row h0 + i) meets input rows h0 - ph + i + a in ring[(i + a) % 3].  Its matrix
+            // instructions for kernel row 0 go first; the ring slot they read is then free for the next step's
+            // new row, which is converted — with the next step's gradients — in the shadow of the matrix
+            // instructions for kernel rows 1 and 2.  Loads run two steps ahead of their conversion.
+            RowOperand<KW> ring[KH];
+            GradOperand A;
+            float nx[2][4 * NCH], ng[2][8];
+            unsigned wl[2], gl[2];
+            load_row(h0 - ph, nx[0], wl[0]);
+            load_row(h0 - ph + 1, nx[1], wl[1]);
+            load_grad(h0, 0, ng[0], gl[0]);
+            convert_row(nx[0], wl[0], ring[0]);
+            load_row(h0 - ph + 2, nx[0], wl[0]);
+            convert_row(nx[1], wl[1], ring[1]);
+            convert_grad(ng[0], gl[0], A);
+            load_row(h0 - ph + 3, nx[1], wl[1]);                 // step 1's new row and gradients
+            load_grad(h0 + 1, 1, ng[1], gl[1]);
+            convert_row(nx[0], wl[0], ring[2]);
+            load_row(h0 - ph + 4, nx[0], wl[0]);                 // step 2's
+            load_grad(h0 + 2, 2, ng[0], gl[0]);
+            auto taps_of_row = [&](int a, const RowOperand<KW> &R) {
+#pragma unroll
+                for (int b = 0; b < KW; ++b) {
                     v16f c = acc[a * KW + b];                    // smallest products first
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a3, b1, c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, b2, c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b3, c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, b1, c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b2, c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.a[2], R.b[b][0], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.a[1], R.b[b][1], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.a[0], R.b[b][2], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.a[1], R.b[b][0], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.a[0], R.b[b][1], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.a[0], R.b[b][0], c, 0, 0, 0);
                     acc[a * KW + b] = c;
                 }
-            }
-            gi += 2;
-            while (gi >= g8) {
-                gi -= g8;
-                if (++ho == Ho) { ho = 0; ++n; }
+            };
+            for (int i6 = 0; i6 < S; i6 += 6) {
+#pragma unroll
+                for (int j6 = 0; j6 < 6; ++j6) {
+                    const int i = i6 + j6, j = j6 % 3;
+                    const int bsel = (j6 + 1) & 1;               // what step i + 1 needs, loaded two steps ago
+                    taps_of_row(0, ring[j]);
+                    GradOperand An;
+                    convert_row(nx[bsel], wl[bsel], ring[j]);    // row h0 - ph + i + 3: kernel row 2 of step i + 1
+                    convert_grad(ng[bsel], gl[bsel], An);
+                    load_row(h0 - ph + i + 5, nx[bsel], wl[bsel]);   // step i + 3's
+                    load_grad(h0 + i + 3, i + 3, ng[bsel], gl[bsel]);
+                    taps_of_row(1, ring[(j + 1) % 3]);
+                    taps_of_row(2, ring[(j + 2) % 3]);
+                    A = An;
+                }
             }
         }
     }
@@ -197,10 +235,10 @@ __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *
             }
         }
         __syncthreads();
-        for (int e = threadIdx.x; e < 16 * ci_n * T; e += kThreads) {
-            const int rl = e / (ci_n * T), in = e - rl * (ci_n * T);
+        for (int rl = 0; rl < 16; ++rl) {
             const int c = co0 + 16 * q + rl;
-            if (c < Cout) atomicAdd(gw + ((int64_t)c * Cin + ci0) * T + in, red[rl][in]);
+            if (c >= Cout) break;
+            for (int in = threadIdx.x; in < ci_n * T; in += kThreads) atomicAdd(gw + ((int64_t)c * Cin + ci0) * T + in, red[rl][in]);
         }
     }
 }
@@ -213,24 +251,40 @@ hipError_t launch_conv2d_gw_split(const float *x, const float *gy, float *gw, in
                                   int32_t ph, int32_t pw, hipStream_t s, bool *taken)
 {
     *taken = false;
-    if (sw != 1 || kh != 3 || kw != 3 || (Cin & 31) || (Cout & 31) || N < 1) return hipSuccess;
+    if (sw != 1 || sh != 1 || kh != 3 || kw != 3 || (Cin & 31) || (Cout & 31) || N < 1) return hipSuccess;
+    if ((W & 3) || (Wo & 3) || (pw != 0 && pw != 1)) return hipSuccess;
     if (g_opt.conv2d_variant != 0 || Cin > 32768 || Cout > 32768) return hipSuccess;
-    if (N * Cout * Ho * Wo < 8 || N * Cin * H * W < 12) return hipSuccess;      // the masked lanes' dummy loads
     const int g8 = (int)((Wo + 7) / 8);
-    const int64_t n_groups = N * Ho * g8;
     const int co_blocks = (int)((Cout + 63) / 64), ci_blocks = (int)((Cin + 63) / 64);
-    // Split of the positions over workgroups: enough to fill the GPU once, no more — every workgroup ends
-    // with atomic adds of its whole block.
-    int64_t split = (int64_t)device_cus() / ((int64_t)co_blocks * ci_blocks);
-    if (split < 1) split = 1;
-    int64_t per = (n_groups + split - 1) / split;
-    per = (per + 1) / 2 * 2;                             // whole pairs of groups
-    split = (n_groups + per - 1) / per;
-    if (split > 2147483647LL || (int64_t)co_blocks * ci_blocks > 65535) return hipSuccess;
+    if ((int64_t)co_blocks * ci_blocks > 65535) return hipSuccess;
+    // Workgroups per block of gw: enough to fill the GPU once, no more — every workgroup ends with atomic adds
+    // of its whole block.  Rows per task S (a multiple of 6: the loop is unrolled over the ring of three rows and
+    // the two load buffers): the one whose rounds of whole tasks cost least,
+    // counting two extra row conversions per task.
+    int64_t wgs = (int64_t)device_cus() / ((int64_t)co_blocks * ci_blocks);
+    if (wgs < 1) wgs = 1;
+    int S = 6, nseg = 1;
+    int64_t pairs = 1, per = 1;
+    double best = 1e300;
+    for (int s3 = 6; s3 <= 30 && s3 < Ho + 6; s3 += 6) {
+        const int ns = (int)((Ho + s3 - 1) / s3);
+        const int64_t pr = (N * g8 * ns + 1) / 2;
+        const int64_t pw_ = (pr + wgs - 1) / wgs;
+        const double cost = (double)pw_ * (s3 + 2 * 0.3);
+        if (cost < best) { best = cost; S = s3; nseg = ns; pairs = pr; per = pw_; }
+    }
+    const int64_t n_tasks = N * g8 * nseg;
+    const int64_t grid = (pairs + per - 1) / per;
+    if (grid > 2147483647LL) return hipSuccess;
     *taken = true;
-    hipLaunchKernelGGL((conv2d_gw_split_kernel<3, 3>), dim3((unsigned)split, (unsigned)(co_blocks * ci_blocks)), dim3(kThreads),
-                       0, s, x, gy, gw, (int)Cin, (int)H, (int)W, (int)Cout, (int)Ho, (int)Wo, sh, ph, pw, g8, n_groups, per,
-                       ci_blocks, N * Cin * H * W);
+    if (pw == 1)
+        hipLaunchKernelGGL((conv2d_gw_split_kernel<3, 3, 1>), dim3((unsigned)grid, (unsigned)(co_blocks * ci_blocks)),
+                           dim3(kThreads), 0, s, x, gy, gw, (int)Cin, (int)H, (int)W, (int)Cout, (int)Ho, (int)Wo, ph, g8, S,
+                           nseg, n_tasks, per, ci_blocks, N * Cin * H * W, N * Cout * Ho * Wo);
+    else
+        hipLaunchKernelGGL((conv2d_gw_split_kernel<3, 3, 0>), dim3((unsigned)grid, (unsigned)(co_blocks * ci_blocks)),
+                           dim3(kThreads), 0, s, x, gy, gw, (int)Cin, (int)H, (int)W, (int)Cout, (int)Ho, (int)Wo, ph, g8, S,
+                           nseg, n_tasks, per, ci_blocks, N * Cin * H * W, N * Cout * Ho * Wo);
     return hipGetLastError();
 }
 
