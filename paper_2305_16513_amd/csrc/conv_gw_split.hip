@@ -213,6 +213,13 @@ __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *
                     taps_of_row(1, ring[(j + 1) % 3]);
                     taps_of_row(2, ring[(j + 2) % 3]);
                     A = An;
+                    // the order asked of the scheduler: a few vector instructions after every matrix instruction,
+                    // so that the conversions hide behind the matrix pipe instead of running in a block of their own
+#pragma unroll
+                    for (int k = 0; k < 6 * T; ++k) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+                    }
                 }
             }
         }
@@ -235,10 +242,21 @@ __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *
             }
         }
         __syncthreads();
-        for (int rl = 0; rl < 16; ++rl) {
+        // all reads of a thread first, then its adds back to back: one read, one add at a time would pay the
+        // LDS latency 36 times over
+        constexpr int NE = 16 * 64 * T / kThreads;
+        static_assert(16 * 64 * T % kThreads == 0, "whole rounds of the workgroup");
+        float val[NE];
+#pragma unroll
+        for (int k = 0; k < NE; ++k) {
+            const int e = k * kThreads + threadIdx.x, rl = e / (64 * T);
+            val[k] = red[rl][e - rl * (64 * T)];
+        }
+#pragma unroll
+        for (int k = 0; k < NE; ++k) {
+            const int e = k * kThreads + threadIdx.x, rl = e / (64 * T), in = e - rl * (64 * T);
             const int c = co0 + 16 * q + rl;
-            if (c >= Cout) break;
-            for (int in = threadIdx.x; in < ci_n * T; in += kThreads) atomicAdd(gw + ((int64_t)c * Cin + ci0) * T + in, red[rl][in]);
+            if (c < Cout && in < ci_n * T) atomicAdd(gw + ((int64_t)c * Cin + ci0) * T + in, val[k]);
         }
     }
 }
@@ -263,6 +281,7 @@ hipError_t launch_conv2d_gw_split(const float *x, const float *gy, float *gw, in
     // counting two extra row conversions per task.
     int64_t wgs = (int64_t)device_cus() / ((int64_t)co_blocks * ci_blocks);
     if (wgs < 1) wgs = 1;
+    if (g_opt.slide_group > 0) wgs = g_opt.slide_group;      // A/B: workgroups per block of gw
     int S = 6, nseg = 1;
     int64_t pairs = 1, per = 1;
     double best = 1e300;
