@@ -1,15 +1,15 @@
 // The adjoint of the dense 2-D convolution with respect to its weights (the training side of
 // Section 2.5's sliding dot product), horizontal stride 1, on the bf16 matrix cores with exactly split
-// fp32 operands (stride 1):
+// fp32 operands (3 x 3, stride s = 1 or 2 on both axes):
 //
-//   gw[co][ci][a][b] = sum over (n, ho, wo) of  gy[n][co][ho][wo] * x[n][ci][ho - ph + a][wo - pw + b]
+//   gw[co][ci][a][b] = sum over (n, ho, wo) of  gy[n][co][ho][wo] * x[n][ci][s*ho - ph + a][s*wo - pw + b]
 //
 // is, for each tap (a, b), a matrix product GY[co][positions] * X_ab[positions][ci] whose contraction
 // index — the position — is also the index that is contiguous in memory for both operands.  The
 // operand layout of v_mfma_f32_32x32x16_bf16 (a lane holds 8 consecutive contraction indices of one row /
 // column) therefore reads straight from memory: a lane loads 8 consecutive gradients of its output
-// channel, and the 8 + KW - 1 consecutive inputs of its input channel that those positions meet under
-// the KW taps of one kernel row; nothing is staged in LDS and no column matrix is built.  Every fp32
+// channel, and the 7s + KW consecutive inputs of its input channel that those positions meet under
+// the KW taps of one kernel row (every s-th of them per tap); nothing is staged in LDS and no column matrix is built.  Every fp32
 // value is split into three bf16 pieces by truncation (8 + 8 + 8 bits of mantissa; the pieces sum to
 // the value exactly) and six of the nine piece products are kept — what is dropped is below 2^-23 of
 // the term — so the result has fp32 accuracy at 6/16 of the fp32 matrix instruction's time.
@@ -17,7 +17,7 @@
 // A workgroup owns a 64 x 64 block of (co, ci) — one 32 x 32 block and all KH*KW taps per wavefront,
 // 16 accumulator registers per tap — and a share of the positions, cut into tasks of a column of 8
 // positions by S output rows (the two halves of a wavefront take two tasks).  Walking down a column, a step
-// converts (splits, packs) one new input row and keeps the two it shares with the step before; that
+// converts (splits, packs) the s new input rows and keeps what it shares with the step before; that
 // conversion runs in the shadow of the matrix instructions, and loads run two steps ahead of it.  At the end the blocks go through LDS, 16 output channels at a time, and leave as atomic
 // adds whose lanes run over contiguous (ci, tap) — adds to one cache line serialise, so as few
 // instructions as possible touch each line.  gw is cleared by the caller first; the order of the adds
@@ -51,16 +51,16 @@ template <int KW> struct RowOperand {
     v8bf b[KW][3];
 };
 
-template <int KH, int KW, int PW>
+template <int KH, int KW, int PW, int ST>
 __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *__restrict__ x, const float *__restrict__ gy,
                                                                    float *__restrict__ gw, int Cin, int H, int W, int Cout,
                                                                    int Ho, int Wo, int ph, int g8, int S, int nseg,
                                                                    int64_t n_tasks, int64_t pairs_per_wg, int ci_blocks,
                                                                    int64_t x_total, int64_t gy_total)
 {
-    static_assert(KH == 3, "the ring of kernel rows below is written for three");
+    static_assert(KH == 3 && (ST == 1 || ST == 2), "the ring of kernel rows below is written for three rows, strides 1 and 2");
     constexpr int T = KH * KW;
-    constexpr int NV = 8 + KW - 1;                   // inputs a lane needs per kernel row
+    constexpr int NV = 7 * ST + KW;                  // inputs a lane needs per kernel row: 8 windows ST apart
     // W and Wo are multiples of 4 and a column starts at a multiple of 8, so the first input a lane needs sits
     // D elements into a 16-byte group of the tensor: loads of whole groups never straddle an end of the tensor
     constexpr int D = (4 - PW % 4) % 4;
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *
             const int wo0 = (int)(col - n * g8) * 8, h0 = seg * S;
             const float *xp = x + (n * Cin + ci) * (int64_t)H * W;       // my input plane
             const float *gp = gy + (n * Cout + co) * (int64_t)Ho * Wo;   // my gradient plane
-            const int p0 = wo0 - PW;
+            const int p0 = ST * wo0 - PW;
             const int64_t x_groups = x_total >> 2, gy_groups = gy_total >> 2;
             // the groups that hold positions p0 .. p0 + NV - 1 of input row r, as loaded (no branches, nothing
             // waits here): groups beyond an end of the tensor are taken from its first / last group, and every
@@ -129,9 +129,9 @@ __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *
                     unsigned Bp[3][4];
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        Bp[0][i] = pack_hi(xv[b + 2 * i], xv[b + 2 * i + 1]);
-                        Bp[1][i] = pack_hi(q2[b + 2 * i], q2[b + 2 * i + 1]);
-                        Bp[2][i] = pack_hi(q3[b + 2 * i], q3[b + 2 * i + 1]);
+                        Bp[0][i] = pack_hi(xv[b + ST * 2 * i], xv[b + ST * (2 * i + 1)]);
+                        Bp[1][i] = pack_hi(q2[b + ST * 2 * i], q2[b + ST * (2 * i + 1)]);
+                        Bp[2][i] = pack_hi(q3[b + ST * 2 * i], q3[b + ST * (2 * i + 1)]);
                     }
 #pragma unroll
                     for (int pc = 0; pc < 3; ++pc)
@@ -166,25 +166,30 @@ __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *
 #pragma unroll
                 for (int pc = 0; pc < 3; ++pc) A.a[pc] = __builtin_bit_cast(v8bf, (v4u){w[pc][0], w[pc][1], w[pc][2], w[pc][3]});
             };
-            // Step i (output row h0 + i) meets input rows h0 - ph + i + a in ring[(i + a) % 3].  Its matrix
-            // instructions for kernel row 0 go first; the ring slot they read is then free for the next step's
-            // new row, which is converted — with the next step's gradients — in the shadow of the matrix
-            // instructions for kernel rows 1 and 2.  Loads run two steps ahead of their conversion.
+            // Step i (output row h0 + i) meets input rows r0 + ST*i + a, r0 = ST*h0 - ph, kept in ring[(ST*i + a) % 3].
+            // Its matrix instructions for the kernel rows whose ring slots the next step does not need (the first ST
+            // of them) go first; those slots then take the next step's new rows, which are converted — with the
+            // next step's gradients — in the shadow of the remaining matrix instructions.  Loads run two steps
+            // ahead of their conversion.
+            const int r0 = ST * h0 - ph;
             RowOperand<KW> ring[KH];
             GradOperand A;
-            float nx[2][4 * NCH], ng[2][8];
-            unsigned wl[2], gl[2];
-            load_row(h0 - ph, nx[0], wl[0]);
-            load_row(h0 - ph + 1, nx[1], wl[1]);
+            float nx[2][ST][4 * NCH], ng[2][8];
+            unsigned wl[2][ST], gl[2];
+            // rows r0 + 0, 1, 2 (step 0), then the new rows of steps 1 and 2 into the two buffers
+#pragma unroll
+            for (int a = 0; a < KH; ++a) {
+                load_row(r0 + a, nx[0][0], wl[0][0]);
+                convert_row(nx[0][0], wl[0][0], ring[a]);
+            }
             load_grad(h0, 0, ng[0], gl[0]);
-            convert_row(nx[0], wl[0], ring[0]);
-            load_row(h0 - ph + 2, nx[0], wl[0]);
-            convert_row(nx[1], wl[1], ring[1]);
             convert_grad(ng[0], gl[0], A);
-            load_row(h0 - ph + 3, nx[1], wl[1]);                 // step 1's new row and gradients
+#pragma unroll
+            for (int u = 0; u < ST; ++u) {
+                load_row(r0 + ST + KH - ST + u, nx[1][u], wl[1][u]);         // step 1's new rows: r0 + ST*1 + (KH - ST + u)
+                load_row(r0 + 2 * ST + KH - ST + u, nx[0][u], wl[0][u]);     // step 2's
+            }
             load_grad(h0 + 1, 1, ng[1], gl[1]);
-            convert_row(nx[0], wl[0], ring[2]);
-            load_row(h0 - ph + 4, nx[0], wl[0]);                 // step 2's
             load_grad(h0 + 2, 2, ng[0], gl[0]);
             auto taps_of_row = [&](int a, const RowOperand<KW> &R) {
 #pragma unroll
@@ -202,23 +207,27 @@ __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *
             for (int i6 = 0; i6 < S; i6 += 6) {
 #pragma unroll
                 for (int j6 = 0; j6 < 6; ++j6) {
-                    const int i = i6 + j6, j = j6 % 3;
+                    const int i = i6 + j6;
                     const int bsel = (j6 + 1) & 1;               // what step i + 1 needs, loaded two steps ago
-                    taps_of_row(0, ring[j]);
+#pragma unroll
+                    for (int a = 0; a < ST; ++a) taps_of_row(a, ring[(ST * j6 + a) % 3]);
                     GradOperand An;
-                    convert_row(nx[bsel], wl[bsel], ring[j]);    // row h0 - ph + i + 3: kernel row 2 of step i + 1
+#pragma unroll
+                    for (int u = 0; u < ST; ++u)                 // step i + 1's kernel row KH - ST + u: the slot of my row u
+                        convert_row(nx[bsel][u], wl[bsel][u], ring[(ST * j6 + u) % 3]);
                     convert_grad(ng[bsel], gl[bsel], An);
-                    load_row(h0 - ph + i + 5, nx[bsel], wl[bsel]);   // step i + 3's
+#pragma unroll
+                    for (int u = 0; u < ST; ++u) load_row(r0 + ST * (i + 3) + KH - ST + u, nx[bsel][u], wl[bsel][u]);   // step i + 3's
                     load_grad(h0 + i + 3, i + 3, ng[bsel], gl[bsel]);
-                    taps_of_row(1, ring[(j + 1) % 3]);
-                    taps_of_row(2, ring[(j + 2) % 3]);
+#pragma unroll
+                    for (int a = ST; a < KH; ++a) taps_of_row(a, ring[(ST * j6 + a) % 3]);
                     A = An;
                     // the order asked of the scheduler: a few vector instructions after every matrix instruction,
                     // so that the conversions hide behind the matrix pipe instead of running in a block of their own
 #pragma unroll
                     for (int k = 0; k < 6 * T; ++k) {
                         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, ST == 1 ? 6 : 8, 0);
                     }
                 }
             }
@@ -269,8 +278,8 @@ hipError_t launch_conv2d_gw_split(const float *x, const float *gy, float *gw, in
                                   int32_t ph, int32_t pw, hipStream_t s, bool *taken)
 {
     *taken = false;
-    if (sw != 1 || sh != 1 || kh != 3 || kw != 3 || (Cin & 31) || (Cout & 31) || N < 1) return hipSuccess;
-    if ((W & 3) || (Wo & 3) || (pw != 0 && pw != 1)) return hipSuccess;
+    if (sw != sh || (sw != 1 && sw != 2) || kh != 3 || kw != 3 || (Cin & 31) || (Cout & 31) || N < 1) return hipSuccess;
+    if ((W & 3) || (Wo & 3) || (pw != 0 && pw != 1) || (sw == 2 && pw != 1)) return hipSuccess;
     if (g_opt.conv2d_variant != 0 || Cin > 32768 || Cout > 32768) return hipSuccess;
     const int g8 = (int)((Wo + 7) / 8);
     const int co_blocks = (int)((Cout + 63) / 64), ci_blocks = (int)((Cin + 63) / 64);
@@ -296,14 +305,14 @@ hipError_t launch_conv2d_gw_split(const float *x, const float *gy, float *gw, in
     const int64_t grid = (pairs + per - 1) / per;
     if (grid > 2147483647LL) return hipSuccess;
     *taken = true;
-    if (pw == 1)
-        hipLaunchKernelGGL((conv2d_gw_split_kernel<3, 3, 1>), dim3((unsigned)grid, (unsigned)(co_blocks * ci_blocks)),
-                           dim3(kThreads), 0, s, x, gy, gw, (int)Cin, (int)H, (int)W, (int)Cout, (int)Ho, (int)Wo, ph, g8, S,
-                           nseg, n_tasks, per, ci_blocks, N * Cin * H * W, N * Cout * Ho * Wo);
-    else
-        hipLaunchKernelGGL((conv2d_gw_split_kernel<3, 3, 0>), dim3((unsigned)grid, (unsigned)(co_blocks * ci_blocks)),
-                           dim3(kThreads), 0, s, x, gy, gw, (int)Cin, (int)H, (int)W, (int)Cout, (int)Ho, (int)Wo, ph, g8, S,
-                           nseg, n_tasks, per, ci_blocks, N * Cin * H * W, N * Cout * Ho * Wo);
+#define SWS_GW_SPLIT(PW_, ST_)                                                                                        \
+    hipLaunchKernelGGL((conv2d_gw_split_kernel<3, 3, PW_, ST_>), dim3((unsigned)grid, (unsigned)(co_blocks * ci_blocks)), \
+                       dim3(kThreads), 0, s, x, gy, gw, (int)Cin, (int)H, (int)W, (int)Cout, (int)Ho, (int)Wo, ph, g8, S,   \
+                       nseg, n_tasks, per, ci_blocks, N * Cin * H * W, N * Cout * Ho * Wo)
+    if (sw == 2) SWS_GW_SPLIT(1, 2);
+    else if (pw == 1) SWS_GW_SPLIT(1, 1);
+    else SWS_GW_SPLIT(0, 1);
+#undef SWS_GW_SPLIT
     return hipGetLastError();
 }
 

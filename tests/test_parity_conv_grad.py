@@ -334,7 +334,11 @@ def test_conv2d_grad_input_on_the_streaming_kernels(B, case, variant):
 # half, vertical strides, no padding, images whose groups split unevenly over the workgroups.
 SPLIT_GW = [(2, 32, 20, 20, 32, 3, 3, 1, 1, 1, 1), (3, 96, 13, 13, 32, 3, 3, 1, 1, 1, 1), (1, 32, 9, 7, 160, 3, 3, 1, 1, 1, 1),
             (5, 64, 11, 30, 64, 3, 3, 2, 1, 1, 1), (2, 128, 10, 19, 64, 3, 3, 1, 1, 0, 0), (7, 32, 3, 3, 32, 3, 3, 1, 1, 1, 1),
-            (2, 64, 17, 9, 96, 3, 3, 3, 1, 0, 2), (1, 32, 3, 5, 32, 3, 3, 1, 1, 0, 0)]
+            (2, 64, 17, 9, 96, 3, 3, 3, 1, 0, 2), (1, 32, 3, 5, 32, 3, 3, 1, 1, 0, 0),
+            # rows in multiples of 4: the kernel's own shapes, stride 1 (pad 0 and 1) and stride 2
+            (2, 32, 12, 16, 32, 3, 3, 1, 1, 0, 0), (3, 64, 9, 24, 32, 3, 3, 1, 1, 1, 1), (1, 32, 40, 8, 64, 3, 3, 1, 1, 1, 1),
+            (2, 32, 28, 28, 32, 3, 3, 2, 2, 1, 1), (3, 64, 16, 24, 96, 3, 3, 2, 2, 1, 1), (1, 32, 8, 8, 32, 3, 3, 2, 2, 1, 1),
+            (2, 32, 13, 16, 64, 3, 3, 2, 2, 1, 1), (5, 32, 56, 56, 32, 3, 3, 2, 2, 1, 1)]
 
 
 @pytest.mark.parametrize("integer", [False, True])
