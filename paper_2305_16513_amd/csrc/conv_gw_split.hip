@@ -51,7 +51,7 @@ template <int KW> struct RowOperand {
     v8bf b[KW][3];
 };
 
-template <int KH, int KW, int PW, int ST>
+template <int KH, int KW, int PW, int ST, bool DYN>
 __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *__restrict__ x, const float *__restrict__ gy,
                                                                    float *__restrict__ gw, int Cin, int H, int W, int Cout,
                                                                    int Ho, int Wo, int ph, int g8, int S, int nseg,
@@ -63,8 +63,11 @@ __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *
     constexpr int NV = 7 * ST + KW;                  // inputs a lane needs per kernel row: 8 windows ST apart
     // W and Wo are multiples of 4 and a column starts at a multiple of 8, so the first input a lane needs sits
     // D elements into a 16-byte group of the tensor: loads of whole groups never straddle an end of the tensor
-    constexpr int D = (4 - PW % 4) % 4;
+    // (DYN: rows of any length — every element is then loaded on its own, from an offset clamped into the lane's
+    // plane)
+    constexpr int D = DYN ? 0 : (4 - PW % 4) % 4;
     constexpr int NCH = (D + NV + 3) / 4;            // groups per kernel row
+    constexpr int NGG = 2;                           // groups per 8 gradients
     __shared__ float red[16][64 * T + 1];
     const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -97,31 +100,44 @@ __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *
             // the groups that hold positions p0 .. p0 + NV - 1 of input row r, as loaded (no branches, nothing
             // waits here): groups beyond an end of the tensor are taken from its first / last group, and every
             // cell outside the plane is zeroed at conversion time (position < wlim)
-            auto load_row = [&](int r, float (&xv)[4 * NCH], unsigned &wlim) {
+            auto load_row = [&](int r, float (&xv)[4 * NCH], unsigned &wlim, unsigned &dsel) {
                 const bool rowok = tv && r >= 0 && r < H;
                 wlim = rowok ? (unsigned)W : 0u;
-                const int64_t g0 = ((xp - x) + (int64_t)(rowok ? r : 0) * W + (p0 - D)) >> 2;    // may be -1
+                dsel = 0;
+                if constexpr (DYN) {
+                    const int o0 = (rowok ? r : 0) * W + p0, last = H * W - 1;
 #pragma unroll
-                for (int j = 0; j < NCH; ++j) {
-                    int64_t g = g0 + j;
-                    g = g < 0 ? 0 : (g >= x_groups ? x_groups - 1 : g);
-                    // only what is used is loaded: a register of a load still in flight that nothing reads would be
-                    // handed out again, and writing it waits for the load
-                    if (4 * j >= D && 4 * j + 4 <= D + NV) {
-                        const v4f q = *(const v4f_u *)(x + 4 * g);
-                        xv[4 * j] = q.x; xv[4 * j + 1] = q.y; xv[4 * j + 2] = q.z; xv[4 * j + 3] = q.w;
-                    } else {
+                    for (int e = 0; e < NV; ++e) {
+                        const int o = o0 + e;
+                        xv[e] = xp[o < 0 ? 0 : (o > last ? last : o)];
+                    }
+                } else {
+                    const int64_t g0 = ((xp - x) + (int64_t)(rowok ? r : 0) * W + (p0 - D)) >> 2;    // may be -1
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (4 * j + e >= D && 4 * j + e < D + NV) xv[4 * j + e] = x[4 * g + e];
+                    for (int j = 0; j < NCH; ++j) {
+                        int64_t g = g0 + j;
+                        g = g < 0 ? 0 : (g >= x_groups ? x_groups - 1 : g);
+                        // only what is used is loaded: a register of a load still in flight that nothing reads would
+                        // be handed out again, and writing it waits for the load
+                        if (4 * j >= D && 4 * j + 4 <= D + NV) {
+                            const v4f q = *(const v4f_u *)(x + 4 * g);
+                            xv[4 * j] = q.x; xv[4 * j + 1] = q.y; xv[4 * j + 2] = q.z; xv[4 * j + 3] = q.w;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (4 * j + e >= D && 4 * j + e < D + NV) xv[4 * j + e] = x[4 * g + e];
+                        }
                     }
                 }
             };
-            auto convert_row = [&](const float (&raw)[4 * NCH], unsigned wlim, RowOperand<KW> &R) {
+            auto convert_row = [&](const float (&raw)[4 * NCH], unsigned wlim, unsigned dsel, RowOperand<KW> &R) {
                 float xv[NV], q2[NV], q3[NV];
+                (void)dsel;
+#pragma unroll
+                for (int e = 0; e < NV; ++e) xv[e] = raw[D + e];
 #pragma unroll
                 for (int e = 0; e < NV; ++e) {
-                    xv[e] = (unsigned)(p0 + e) < wlim ? raw[D + e] : 0.0f;
+                    xv[e] = (unsigned)(p0 + e) < wlim ? xv[e] : 0.0f;
                     split3(xv[e], q2[e], q3[e]);
                 }
 #pragma unroll
@@ -140,20 +156,32 @@ __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *
             };
             // 8 consecutive gradients of output row ho, as loaded; glim = how many of them count (none beyond the
             // segment or the plane)
-            auto load_grad = [&](int ho, int i, float (&ga)[8], unsigned &glim) {
+            auto load_grad = [&](int ho, int i, float (&ga)[4 * NGG], unsigned &glim) {
                 const bool ok_row = tv && i < S && ho < Ho;
                 glim = ok_row ? (unsigned)(Wo - wo0) : 0u;
-                const int64_t g0 = ((gp - gy) + (int64_t)(ok_row ? ho : 0) * Wo + wo0) >> 2;
-                const int64_t g1 = g0 + 1 < gy_groups ? g0 + 1 : gy_groups - 1;
-                const v4f a0 = *(const v4f_u *)(gy + 4 * g0), a1 = *(const v4f_u *)(gy + 4 * g1);
-                ga[0] = a0.x; ga[1] = a0.y; ga[2] = a0.z; ga[3] = a0.w; ga[4] = a1.x; ga[5] = a1.y; ga[6] = a1.z; ga[7] = a1.w;
+                if constexpr (DYN) {
+                    const int o0 = (ok_row ? ho : 0) * Wo + wo0, last = Ho * Wo - 1;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) ga[e] = gp[o0 + e > last ? last : o0 + e];
+                } else {
+                    const int64_t g0 = ((gp - gy) + (int64_t)(ok_row ? ho : 0) * Wo + wo0) >> 2;
+#pragma unroll
+                    for (int j = 0; j < NGG; ++j) {
+                        const int64_t g = g0 + j < gy_groups ? g0 + j : gy_groups - 1;
+                        const v4f q = *(const v4f_u *)(gy + 4 * g);
+                        ga[4 * j] = q.x; ga[4 * j + 1] = q.y; ga[4 * j + 2] = q.z; ga[4 * j + 3] = q.w;
+                    }
+                }
             };
             struct GradOperand { v8bf a[3]; };
-            auto convert_grad = [&](const float (&raw)[8], unsigned glim, GradOperand &A) {
+            auto convert_grad = [&](const float (&raw)[4 * NGG], unsigned gl_, GradOperand &A) {
                 float ga[8], p2[8], p3[8];
+                const unsigned glim = gl_;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ga[e] = raw[e];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    ga[e] = (unsigned)e < glim ? raw[e] : 0.0f;
+                    ga[e] = (unsigned)e < glim ? ga[e] : 0.0f;
                     split3(ga[e], p2[e], p3[e]);
                 }
                 unsigned w[3][4];
@@ -174,23 +202,23 @@ __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *
             const int r0 = ST * h0 - ph;
             RowOperand<KW> ring[KH];
             GradOperand A;
-            float nx[2][ST][4 * NCH], ng[2][8];
-            unsigned wl[2][ST], gl[2];
+            constexpr int NB = 2;                                // steps the loads run ahead
+            float nx[NB][ST][4 * NCH], ng[NB][4 * NGG];
+            unsigned wl[NB][ST], dl[NB][ST], gl[NB];
             // rows r0 + 0, 1, 2 (step 0), then the new rows of steps 1 and 2 into the two buffers
 #pragma unroll
             for (int a = 0; a < KH; ++a) {
-                load_row(r0 + a, nx[0][0], wl[0][0]);
-                convert_row(nx[0][0], wl[0][0], ring[a]);
+                load_row(r0 + a, nx[0][0], wl[0][0], dl[0][0]);
+                convert_row(nx[0][0], wl[0][0], dl[0][0], ring[a]);
             }
             load_grad(h0, 0, ng[0], gl[0]);
             convert_grad(ng[0], gl[0], A);
 #pragma unroll
-            for (int u = 0; u < ST; ++u) {
-                load_row(r0 + ST + KH - ST + u, nx[1][u], wl[1][u]);         // step 1's new rows: r0 + ST*1 + (KH - ST + u)
-                load_row(r0 + 2 * ST + KH - ST + u, nx[0][u], wl[0][u]);     // step 2's
+            for (int k = 1; k <= NB; ++k) {                      // the new rows and gradients of steps 1 .. NB
+#pragma unroll
+                for (int u = 0; u < ST; ++u) load_row(r0 + k * ST + KH - ST + u, nx[k % NB][u], wl[k % NB][u], dl[k % NB][u]);
+                load_grad(h0 + k, k, ng[k % NB], gl[k % NB]);
             }
-            load_grad(h0 + 1, 1, ng[1], gl[1]);
-            load_grad(h0 + 2, 2, ng[0], gl[0]);
             auto taps_of_row = [&](int a, const RowOperand<KW> &R) {
 #pragma unroll
                 for (int b = 0; b < KW; ++b) {
@@ -208,17 +236,18 @@ __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *
 #pragma unroll
                 for (int j6 = 0; j6 < 6; ++j6) {
                     const int i = i6 + j6;
-                    const int bsel = (j6 + 1) & 1;               // what step i + 1 needs, loaded two steps ago
+                    if (i >= S) break;                           // S need not be a whole number of rounds
+                    const int bsel = (j6 + 1) % NB;              // what step i + 1 needs, loaded NB steps ago
 #pragma unroll
                     for (int a = 0; a < ST; ++a) taps_of_row(a, ring[(ST * j6 + a) % 3]);
                     GradOperand An;
 #pragma unroll
                     for (int u = 0; u < ST; ++u)                 // step i + 1's kernel row KH - ST + u: the slot of my row u
-                        convert_row(nx[bsel][u], wl[bsel][u], ring[(ST * j6 + u) % 3]);
+                        convert_row(nx[bsel][u], wl[bsel][u], dl[bsel][u], ring[(ST * j6 + u) % 3]);
                     convert_grad(ng[bsel], gl[bsel], An);
 #pragma unroll
-                    for (int u = 0; u < ST; ++u) load_row(r0 + ST * (i + 3) + KH - ST + u, nx[bsel][u], wl[bsel][u]);   // step i + 3's
-                    load_grad(h0 + i + 3, i + 3, ng[bsel], gl[bsel]);
+                    for (int u = 0; u < ST; ++u) load_row(r0 + ST * (i + 1 + NB) + KH - ST + u, nx[bsel][u], wl[bsel][u], dl[bsel][u]);   // step i + 1 + NB's
+                    load_grad(h0 + i + 1 + NB, i + 1 + NB, ng[bsel], gl[bsel]);
 #pragma unroll
                     for (int a = ST; a < KH; ++a) taps_of_row(a, ring[(ST * j6 + a) % 3]);
                     A = An;
@@ -279,39 +308,45 @@ hipError_t launch_conv2d_gw_split(const float *x, const float *gy, float *gw, in
 {
     *taken = false;
     if (sw != sh || (sw != 1 && sw != 2) || kh != 3 || kw != 3 || (Cin & 31) || (Cout & 31) || N < 1) return hipSuccess;
-    if ((W & 3) || (Wo & 3) || (pw != 0 && pw != 1) || (sw == 2 && pw != 1)) return hipSuccess;
+    if ((pw != 0 && pw != 1) || (sw == 2 && pw != 1) || W >= (1 << 28)) return hipSuccess;
+    const bool dyn = (W & 3) || (Wo & 3);
     if (g_opt.conv2d_variant != 0 || Cin > 32768 || Cout > 32768) return hipSuccess;
     const int g8 = (int)((Wo + 7) / 8);
     const int co_blocks = (int)((Cout + 63) / 64), ci_blocks = (int)((Cin + 63) / 64);
     if ((int64_t)co_blocks * ci_blocks > 65535) return hipSuccess;
     // Workgroups per block of gw: enough to fill the GPU once, no more — every workgroup ends with atomic adds
-    // of its whole block.  Rows per task S (a multiple of 6: the loop is unrolled over the ring of three rows and
-    // the two load buffers): the one whose rounds of whole tasks cost least,
-    // counting two extra row conversions per task.
+    // of its whole block.  Rows per task S: the one whose rounds of whole tasks cost least, counting a step and a
+    // half for a task's start (three rows loaded and converted with nothing to hide behind).
     int64_t wgs = (int64_t)device_cus() / ((int64_t)co_blocks * ci_blocks);
     if (wgs < 1) wgs = 1;
     if (g_opt.slide_group > 0) wgs = g_opt.slide_group;      // A/B: workgroups per block of gw
-    int S = 6, nseg = 1;
+    int S = 1, nseg = (int)Ho;
     int64_t pairs = 1, per = 1;
     double best = 1e300;
-    for (int s3 = 6; s3 <= 30 && s3 < Ho + 6; s3 += 6) {
-        const int ns = (int)((Ho + s3 - 1) / s3);
+    for (int s1 = 1; s1 <= 32 && s1 <= Ho; ++s1) {
+        const int ns = (int)((Ho + s1 - 1) / s1);
         const int64_t pr = (N * g8 * ns + 1) / 2;
         const int64_t pw_ = (pr + wgs - 1) / wgs;
-        const double cost = (double)pw_ * (s3 + 2 * 0.3);
-        if (cost < best) { best = cost; S = s3; nseg = ns; pairs = pr; per = pw_; }
+        const double cost = (double)pw_ * (s1 + 1.5);
+        if (cost < best) { best = cost; S = s1; nseg = ns; pairs = pr; per = pw_; }
     }
     const int64_t n_tasks = N * g8 * nseg;
     const int64_t grid = (pairs + per - 1) / per;
     if (grid > 2147483647LL) return hipSuccess;
     *taken = true;
-#define SWS_GW_SPLIT(PW_, ST_)                                                                                        \
-    hipLaunchKernelGGL((conv2d_gw_split_kernel<3, 3, PW_, ST_>), dim3((unsigned)grid, (unsigned)(co_blocks * ci_blocks)), \
+#define SWS_GW_SPLIT(PW_, ST_, DYN_)                                                                                  \
+    hipLaunchKernelGGL((conv2d_gw_split_kernel<3, 3, PW_, ST_, DYN_>), dim3((unsigned)grid, (unsigned)(co_blocks * ci_blocks)), \
                        dim3(kThreads), 0, s, x, gy, gw, (int)Cin, (int)H, (int)W, (int)Cout, (int)Ho, (int)Wo, ph, g8, S,   \
                        nseg, n_tasks, per, ci_blocks, N * Cin * H * W, N * Cout * Ho * Wo)
-    if (sw == 2) SWS_GW_SPLIT(1, 2);
-    else if (pw == 1) SWS_GW_SPLIT(1, 1);
-    else SWS_GW_SPLIT(0, 1);
+    if (dyn) {
+        if (sw == 2) SWS_GW_SPLIT(1, 2, true);
+        else if (pw == 1) SWS_GW_SPLIT(1, 1, true);
+        else SWS_GW_SPLIT(0, 1, true);
+    } else {
+        if (sw == 2) SWS_GW_SPLIT(1, 2, false);
+        else if (pw == 1) SWS_GW_SPLIT(1, 1, false);
+        else SWS_GW_SPLIT(0, 1, false);
+    }
 #undef SWS_GW_SPLIT
     return hipGetLastError();
 }

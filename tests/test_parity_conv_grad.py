@@ -338,7 +338,10 @@ SPLIT_GW = [(2, 32, 20, 20, 32, 3, 3, 1, 1, 1, 1), (3, 96, 13, 13, 32, 3, 3, 1, 
             # rows in multiples of 4: the kernel's own shapes, stride 1 (pad 0 and 1) and stride 2
             (2, 32, 12, 16, 32, 3, 3, 1, 1, 0, 0), (3, 64, 9, 24, 32, 3, 3, 1, 1, 1, 1), (1, 32, 40, 8, 64, 3, 3, 1, 1, 1, 1),
             (2, 32, 28, 28, 32, 3, 3, 2, 2, 1, 1), (3, 64, 16, 24, 96, 3, 3, 2, 2, 1, 1), (1, 32, 8, 8, 32, 3, 3, 2, 2, 1, 1),
-            (2, 32, 13, 16, 64, 3, 3, 2, 2, 1, 1), (5, 32, 56, 56, 32, 3, 3, 2, 2, 1, 1)]
+            (2, 32, 13, 16, 64, 3, 3, 2, 2, 1, 1), (5, 32, 56, 56, 32, 3, 3, 2, 2, 1, 1),
+            # rows of any length: every element loaded on its own
+            (2, 32, 14, 14, 32, 3, 3, 1, 1, 1, 1), (3, 64, 7, 7, 32, 3, 3, 1, 1, 1, 1), (2, 32, 14, 14, 32, 3, 3, 2, 2, 1, 1),
+            (1, 32, 9, 13, 32, 3, 3, 1, 1, 0, 0), (2, 32, 15, 10, 64, 3, 3, 2, 2, 1, 1), (40, 32, 3, 3, 32, 3, 3, 1, 1, 1, 1)]
 
 
 @pytest.mark.parametrize("integer", [False, True])
