@@ -214,7 +214,7 @@ def sweeps_table(torch, B, workloads, iters=20):
     2*k FLOP per output; the vector-ALU peak without packed fp32 is 78.6 TFLOP/s."""
     g = lambda a: torch.from_numpy(a).cuda()
     out = {"filter_sweep": {}, "dilated_single": {}, "dilated_batched": {}, "pair_operator": {}, "same_size_pooling": {},
-           "storage_16bit": {}, "short_rows": {}, "adjoints": {}}
+           "long_windows": {}, "storage_16bit": {}, "short_rows": {}, "adjoints": {}}
     c6 = workloads.CONFIGS[6]
     rows, length = c6.x_shape[0], c6.x_shape[2]
     x6 = g(workloads.make(6)[0])
@@ -285,6 +285,19 @@ def sweeps_table(torch, B, workloads, iters=20):
                                                                     "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
             del y
     del u, v
+    torch.cuda.empty_cache()
+    # windows longer than a wave tile (one pass: suffix sums of the tile, one shared middle reduction, prefix sums
+    # where the windows end) on a quarter of configuration 5's rows
+    xl = torch.rand(8192, LEN5, device="cuda")
+    for op, opn in ((0, "avg"), (1, "max")):
+        for w in (512, 1024, 2048, 8192):
+            y = torch.empty(8192, LEN5 - w + 1, device="cuda")
+            ms = time_launches(torch, lambda: B.sws_slide1d(op, xl, w, 1.0 / w, y=y), iters)
+            nb = 4 * (xl.numel() + y.numel())
+            out["long_windows"]["%s_w%d" % (opn, w)] = {"ms": round(ms, 4), "GBps": round(nb / ms / 1e6, 1),
+                                                        "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+            del y
+    del xl
     torch.cuda.empty_cache()
     # configuration 5's depthwise layer with 15 mirrored elements at both ends of every row (sws_conv1d_padded)
     x5, t5 = workloads.make(5)
@@ -543,6 +556,12 @@ def run_only(torch, B, workloads, name, steps, cold=False):
         x, taps = g(x_host), g(taps_host)
         y = torch.empty(256, 128, LEN5, device="cuda")
         fn = lambda: B.sws_conv1d_padded(x, taps, 1, K5 // 2, K5 // 2, 1, CH5, mode, y=y)
+    elif name.startswith("long_"):                        # long_<add|max>_w<w>: 8192 rows of 16384, windows longer than a tile
+        _, opn, wn = name.split("_")
+        w = int(wn[1:])
+        xl = torch.rand(8192, LEN5, device="cuda")
+        y = torch.empty(8192, LEN5 - w + 1, device="cuda")
+        fn = lambda: B.sws_slide1d(0 if opn == "add" else 1, xl, w, 1.0 / w, y=y)
     elif name.startswith("slide_") or name == "dwconv_k31":
         x_host, taps_host = workloads.make(5)
         x = g(x_host)

@@ -202,9 +202,9 @@ def test_graph_replay_matches_eager(B):
 @pytest.mark.parametrize("op", [0, 1, 2])
 @pytest.mark.parametrize("w,length", [(851, 2000), (962, 2000), (1500, 1500), (1537, 7000), (2048, 20000), (5000, 20011),
                                       (16384, 16385)])
-def test_windows_longer_than_a_tile_run_as_a_chain(B, op, w, length):
-    """w > 961: the window is split into links within the scan kernel's reach, each link combined
-    with the earlier ones in y (operand order kept: add within tolerance, max / min bit-exact)."""
+def test_windows_longer_than_a_tile(B, op, w, length):
+    """w > 850 on the default route: the one-pass long-window kernel up to 8192, beyond it the window split into
+    links within the scan kernel's reach, each link combined with the earlier ones in y."""
     r = np.random.Generator(np.random.PCG64(op * 100000 + w))
     x = (r.random((3, length), dtype=np.float32) * 2 - 1).astype(np.float32)
     y = to_host(B.sws_slide1d(op, to_gpu(x), w, 1.0 / w))
@@ -222,6 +222,39 @@ def test_windows_longer_than_a_tile_run_as_a_chain(B, op, w, length):
         assert_within_tol(y1, ref, mag, "direct add w=%d" % w)
     else:
         assert_bit_exact(y1, ref, "direct op %d w=%d" % (op, w))
+
+
+@pytest.mark.parametrize("op", [0, 1, 2])
+@pytest.mark.parametrize("w,length", [(513, 513), (600, 3000), (1024, 5000), (1025, 1025), (1025, 1026), (1026, 9000), (2047, 4100),
+                                      (2048, 16384), (4097, 13000), (8192, 16384), (8192, 8200)])
+def test_long_window_kernel_and_chain_agree_with_the_oracle(B, op, w, length):
+    """Windows longer than a wave tile: the one-pass kernel (slide_variant 8: suffix sums of the tile, one shared
+    middle reduction, prefix sums where the windows end) and the chain of shorter windows (slide_variant 5)."""
+    r = np.random.Generator(np.random.PCG64(op * 7 + w + length))
+    x = (r.random((5, length), dtype=np.float32) * 2 - 1).astype(np.float32)
+    ref, mag = oracle.slide1d(op, x, w, 1.0 / w)
+    for variant in (8, 5):
+        B.sws_set_option("slide_variant", variant)
+        try:
+            y = to_host(B.sws_slide1d(op, to_gpu(x), w, 1.0 / w))
+        finally:
+            B.sws_set_option("slide_variant", 0)
+        if op == 0:
+            assert_within_tol(y, ref, mag, "variant %d add w=%d" % (variant, w))
+        else:
+            assert_bit_exact(y, ref, "variant %d op %d w=%d" % (variant, op, w))
+
+
+def test_long_window_kernel_on_integer_valued_input_is_exact(B):
+    x = workloads.integer_valued((3, 20000), -8, 8, seed=13)
+    for w in (700, 1500, 3001, 8000):
+        B.sws_set_option("slide_variant", 8)
+        try:
+            y = to_host(B.sws_slide1d(0, to_gpu(x), w, 1.0))
+        finally:
+            B.sws_set_option("slide_variant", 0)
+        ref, _ = oracle.slide1d(0, x, w, 1.0)
+        assert np.array_equal(y.astype(np.float64), ref), w
 
 
 def test_chain_on_integer_valued_input_is_exact(B):
