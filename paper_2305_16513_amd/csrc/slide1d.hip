@@ -550,7 +550,6 @@ hipError_t launch_chain_padded(const float *x, float *y, int64_t rows, int len, 
 
 constexpr int kDirectMaxW = 11;                      // widest window of the shifted-load kernel (four 128-bit loads per lane)
 constexpr int kScanMaxW = kWave * 16 - 64 + 1;      // leaves at least 64 outputs per wave tile
-constexpr int kChainMinW = 850;                     // longer windows: one pass of the long-window kernel, or a chain of shorter ones
 constexpr int kLongMinW = 449;                      // from here the long-window kernel beats the scan kernel (16384-long rows: w = 400 level, 512 1.1-1.4 x, 850 3 x)
 constexpr int kLongMaxW = 8192;                     // the long-window kernel reads w - 1 extra inputs per tile: beyond this the chain moves less
 
@@ -567,9 +566,9 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
     if (variant == 3 && (w < 2 || w > kScanMaxW)) variant = 0;
     if (variant == 4) return launch_slide1d_generic(op, x, y, rows, len64, w, scale, s);   // generic-operator kernel (A/B)
     if (variant == 7 && w > slide1d_rows_max_w()) variant = 0;
-    if (variant == 8 && (padded || w <= 256)) variant = 0;         // the long-window kernel: plain rows, w > 256
-    // Measured on 16384-long rows: beyond w = 850 two links of half the width beat one pass whose
-    // tiles are mostly halo.
+    if (variant == 8 && (w <= 256 || (padded && pad_mode == SWS_PAD_SHRINK))) variant = 0;   // the long-window kernel: w > 256
+    // Measured on 16384-long rows: the scan kernel's tiles are more and more halo as w grows; from w = 449 the
+    // long-window kernel takes over, beyond its reach a chain of shorter windows.
     if (variant == 0) {
         // Windows up to 9 on short rows (every fifth tile of a 4096-long row is a border tile of
         // the scan kernel) or on small problems (latency-bound: fewer phases per tile): the
@@ -597,14 +596,14 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
         if (short_rows) variant = 7;
         else if (w == 1) variant = padded ? 1 : 2;
         else if (padded && pad_mode == SWS_PAD_SHRINK) variant = w <= kScanMaxW ? 3 : 1;   // one pass rescales by the real elements
-        else if (padded) variant = w <= kChainMinW ? 3 : 6;   // 6: a chain over extended rows
+        else if (padded) variant = w < kLongMinW ? 3 : (w <= kLongMaxW ? 8 : 6);   // 6: a chain over extended rows
         else if (small_w) variant = 2;
         else variant = w < kLongMinW ? 3 : (w <= kLongMaxW ? 8 : 5);
     }
     if (variant == 8) {
-        const hipError_t e = launch_slide1d_long(op, x, y, rows, len, lo, w, scale, s);
+        const hipError_t e = launch_slide1d_long(op, x, y, rows, len, lo, w, scale, padded, pad_left, pad_mode, lv, s);
         if (e != kNotTaken) return e;
-        variant = 5;
+        variant = padded ? 6 : 5;
     }
     if (variant == 5) {                              // longer than a tile: a chain of windows
         if (padded || w < 4) variant = 1;

@@ -29,10 +29,13 @@ __device__ __forceinline__ float lane_read(float v, int src)        // v of lane
     return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(4 * src, __builtin_bit_cast(int, v)));
 }
 
-template <int OP, int NS>
+// PADDED: the windows slide over the row extended by pad_left elements in front (and more behind, lv in all)
+// under the boundary rule pad_mode; an element of the extended row is read from the row element the rule names.
+template <int OP, int NS, bool PADDED>
 __global__ __launch_bounds__(kThreads) void slide_long_kernel(const float *__restrict__ x, float *__restrict__ y, int len,
                                                               int lo, int w, float scale, int tiles_per_row,
-                                                              int64_t n_tiles, int64_t n_units)
+                                                              int64_t n_tiles, int64_t n_units, int pad_left, int pad_mode,
+                                                              int lv)
 {
     using O = Op<OP>;
     constexpr int B = 256 * NS;                      // outputs per tile
@@ -46,8 +49,19 @@ __global__ __launch_bounds__(kThreads) void slide_long_kernel(const float *__res
     const float *xr = x + r * (int64_t)len;
     float *yr = y + r * (int64_t)lo;
     const v4f id4 = {O::id(), O::id(), O::id(), O::id()};
-    // four elements at row index p .. p + 3, the identity beyond the row
+    // four elements at index p .. p + 3 of the (extended) row, the identity beyond it
     auto load4 = [&](int p) -> v4f {
+        if (PADDED) {
+            const int q = p - pad_left;              // index in the physical row
+            if (q >= 0 && q + 4 <= len) return *(const v4f_u *)(xr + q);
+            float e[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int src = p + u < lv ? pad_src(p + u, len, pad_left, pad_mode) : -1;
+                e[u] = src >= 0 ? xr[src] : O::id();
+            }
+            return (v4f){e[0], e[1], e[2], e[3]};
+        }
         if (p + 4 <= len) return *(const v4f_u *)(xr + p);
         v4f v = id4;
         if (p < len) v.x = xr[p];
@@ -151,7 +165,8 @@ __global__ __launch_bounds__(kThreads) void slide_long_kernel(const float *__res
 }
 
 template <int OP, int NS>
-hipError_t launch_long(const float *x, float *y, int64_t rows, int len, int lo, int w, float scale, hipStream_t s)
+hipError_t launch_long(const float *x, float *y, int64_t rows, int len, int lo, int w, float scale, bool padded,
+                       int pad_left, int pad_mode, int lv, hipStream_t s)
 {
     constexpr int B = 256 * NS;
     const int tiles_per_row = (lo + B - 1) / B;
@@ -159,38 +174,34 @@ hipError_t launch_long(const float *x, float *y, int64_t rows, int len, int lo, 
     const int64_t n_units = (n_tiles + kWavesPerWg - 1) / kWavesPerWg;
     const int64_t grid = xcd_grid(n_units);
     if (grid > 2147483647LL) return kNotTaken;
-    hipLaunchKernelGGL((slide_long_kernel<OP, NS>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo, w, scale,
-                       tiles_per_row, n_tiles, n_units);
+    if (padded)
+        hipLaunchKernelGGL((slide_long_kernel<OP, NS, true>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo, w,
+                           scale, tiles_per_row, n_tiles, n_units, pad_left, pad_mode, lv);
+    else
+        hipLaunchKernelGGL((slide_long_kernel<OP, NS, false>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo, w,
+                           scale, tiles_per_row, n_tiles, n_units, 0, 0, len);
     return hipGetLastError();
 }
 
 }  // namespace
 
-// Windows of more than 256 elements on plain rows (tiles of 256, 512 or 1024 outputs: the largest the window
-// exceeds); kNotTaken: a shorter window, or a grid beyond the launch limit.
+// Windows of more than 256 elements (tiles of 256, 512 or 1024 outputs: the largest the window exceeds), on plain
+// rows or on rows extended by the identity / mirror / periodic / edge rule (lv = len + pads, lo = lv - w + 1
+// outputs); kNotTaken: a shorter window, the shrinking-window mode, or a grid beyond the launch limit.
 hipError_t launch_slide1d_long(int op, const float *x, float *y, int64_t rows, int len, int lo, int w, float scale,
-                               hipStream_t s)
+                               bool padded, int pad_left, int pad_mode, int lv, hipStream_t s)
 {
-    if (w <= 256) return kNotTaken;
-    if (w <= 512) {
-        switch (op) {
-        case SWS_OP_ADD: return launch_long<SWS_OP_ADD, 1>(x, y, rows, len, lo, w, scale, s);
-        case SWS_OP_MAX: return launch_long<SWS_OP_MAX, 1>(x, y, rows, len, lo, w, scale, s);
-        default: return launch_long<SWS_OP_MIN, 1>(x, y, rows, len, lo, w, scale, s);
-        }
+    if (w <= 256 || (padded && pad_mode == SWS_PAD_SHRINK)) return kNotTaken;
+#define SWS_LONG(NS_)                                                                                              \
+    switch (op) {                                                                                                  \
+    case SWS_OP_ADD: return launch_long<SWS_OP_ADD, NS_>(x, y, rows, len, lo, w, scale, padded, pad_left, pad_mode, lv, s); \
+    case SWS_OP_MAX: return launch_long<SWS_OP_MAX, NS_>(x, y, rows, len, lo, w, scale, padded, pad_left, pad_mode, lv, s); \
+    default: return launch_long<SWS_OP_MIN, NS_>(x, y, rows, len, lo, w, scale, padded, pad_left, pad_mode, lv, s);         \
     }
-    if (w > 1024) {                                  // w > B is what the decomposition needs
-        switch (op) {
-        case SWS_OP_ADD: return launch_long<SWS_OP_ADD, 4>(x, y, rows, len, lo, w, scale, s);
-        case SWS_OP_MAX: return launch_long<SWS_OP_MAX, 4>(x, y, rows, len, lo, w, scale, s);
-        default: return launch_long<SWS_OP_MIN, 4>(x, y, rows, len, lo, w, scale, s);
-        }
-    }
-    switch (op) {
-    case SWS_OP_ADD: return launch_long<SWS_OP_ADD, 2>(x, y, rows, len, lo, w, scale, s);
-    case SWS_OP_MAX: return launch_long<SWS_OP_MAX, 2>(x, y, rows, len, lo, w, scale, s);
-    default: return launch_long<SWS_OP_MIN, 2>(x, y, rows, len, lo, w, scale, s);
-    }
+    if (w <= 512) { SWS_LONG(1) }
+    if (w <= 1024) { SWS_LONG(2) }
+    SWS_LONG(4)
+#undef SWS_LONG
 }
 
 }  // namespace sws

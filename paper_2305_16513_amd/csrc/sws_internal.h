@@ -113,9 +113,10 @@ hipError_t launch_pool2d_small(int op, const float *x, float *y, int64_t planes,
 int slide1d_rows_max_w();
 hipError_t launch_slide1d_rows(int op, const float *x, float *y, int64_t rows, int len, int lo, int32_t w, float scale,
                                bool padded, int pad_left, int pad_mode, hipStream_t s);
-// Windows longer than a wave tile in one pass (slide_long.hip): plain rows, w > 256; kNotTaken otherwise.
+// Windows longer than a wave tile in one pass (slide_long.hip): w > 256, plain rows or rows extended by a boundary
+// rule other than the shrinking window; kNotTaken otherwise.
 hipError_t launch_slide1d_long(int op, const float *x, float *y, int64_t rows, int len, int lo, int w, float scale,
-                               hipStream_t s);
+                               bool padded, int pad_left, int pad_mode, int lv, hipStream_t s);
 hipError_t launch_slide1d_generic(int op, const float *x, float *y, int64_t rows, int64_t len, int32_t w, float scale,
                                   hipStream_t s);
 hipError_t launch_pool2d(int op, const float *x, float *y, int64_t planes, int64_t H, int64_t W,

@@ -60,10 +60,27 @@ def test_padded_short_rows_and_extreme_pads(B, mode):
 @pytest.mark.parametrize("op", [0, 1, 2])
 @pytest.mark.parametrize("w,pl,pr,length", [(962, 481, 480, 3000), (2000, 999, 1000, 5003), (2049, 0, 2048, 2100), (5000, 4000, 999, 6001),
                                             (1500, 1499, 0, 1600)])
-def test_padded_windows_longer_than_a_tile_run_as_a_chain_over_the_extended_row(B, mode, op, w, pl, pr, length):
+def test_padded_windows_longer_than_a_tile(B, mode, op, w, pl, pr, length):
+    """The default route (one pass of the long-window kernel, its loads through the boundary rule), the chain over the
+    extended row (slide_variant 6) and the long-window kernel forced (8)."""
     r = _rng(mode * 7 + op * 3 + w)
     x = (r.random((3, length), dtype=np.float32) * 2 - 1).astype(np.float32)
-    _check(B, op, x, w, pl, pr, mode, "chain mode=%d op=%d w=%d pads=(%d,%d) len=%d" % (mode, op, w, pl, pr, length))
+    _check(B, op, x, w, pl, pr, mode, "long mode=%d op=%d w=%d pads=(%d,%d) len=%d" % (mode, op, w, pl, pr, length))
+    for variant in (6, 8):
+        B.sws_set_option("slide_variant", variant)
+        try:
+            _check(B, op, x, w, pl, pr, mode, "variant %d mode=%d op=%d w=%d pads=(%d,%d) len=%d" % (variant, mode, op, w, pl, pr, length))
+        finally:
+            B.sws_set_option("slide_variant", 0)
+
+
+@pytest.mark.parametrize("mode", [1, 2, 3])
+def test_same_size_pooling_with_long_windows(B, mode):
+    r = _rng(90 + mode)
+    x = (r.random((4, 9000), dtype=np.float32) * 2 - 1).astype(np.float32)
+    for w in (513, 1025, 2049, 8191):
+        for op in (0, 1):
+            _check(B, op, x, w, w // 2, w // 2, mode, "same-size w=%d" % w)
 
 
 def test_padded_zero_pads_match_the_unpadded_entry_point(B):
