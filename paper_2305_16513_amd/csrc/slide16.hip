@@ -411,6 +411,7 @@ hipError_t launch_16_direct(const T *x, T *y, int64_t rows, int len, int lo, int
 }
 
 constexpr int kScanMaxW = kN - 64 + 1;               // leaves at least 64 outputs per wave tile
+constexpr int kLong16MinW = 600;                     // from here the long-window kernel (bf16, 16384-long rows: w = 513 level, 700 1.3 x, 961 5 x the scan)
 
 template <int OP, typename T>
 hipError_t launch_16(const T *x, T *y, int64_t rows, int len, int lo, int w, float scale, hipStream_t s)
@@ -472,6 +473,13 @@ hipError_t launch_slide1d_16(int op, int dtype, const void *x, void *y, int64_t 
                              float scale, hipStream_t s)
 {
     const int len = (int)len64, lo = len - w + 1;
+    // windows longer than a wave tile: the one-pass long-window kernel (slide_long.hip); slide_variant 8 takes it
+    // from w = 257, 1 and 5 keep it out
+    const int variant = g_opt.slide_variant;
+    if ((w >= kLong16MinW || (variant == 8 && w > 256)) && variant != 1 && variant != 5) {
+        const hipError_t e = launch_slide1d_long_16(op, dtype, x, y, rows, len, lo, w, scale, s);
+        if (e != kNotTaken) return e;
+    }
     if (dtype == SWS_DTYPE_BF16) return launch_16_op<__bf16>(op, x, y, rows, len, lo, w, scale, s);
     return launch_16_op<_Float16>(op, x, y, rows, len, lo, w, scale, s);
 }

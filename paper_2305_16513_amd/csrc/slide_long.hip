@@ -24,6 +24,24 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWavesPerWg = kThreads / kWave;
 
+// Four consecutive elements of a row in memory: fp32, or bf16 / fp16 widened exactly on the way in and rounded
+// to nearest even once on the way out.
+template <typename T> struct Quad;
+template <> struct Quad<float> {
+    static __device__ __forceinline__ v4f load(const float *p) { return *(const v4f_u *)p; }
+    static __device__ __forceinline__ float load1(const float *p) { return *p; }
+    static __device__ __forceinline__ void store(float *p, v4f o) { __builtin_nontemporal_store(o, (v4f_u *)p); }
+    static __device__ __forceinline__ void store1(float *p, float o) { *p = o; }
+};
+template <typename T> struct Quad {
+    typedef T v4 __attribute__((ext_vector_type(4)));
+    typedef v4 v4_u __attribute__((aligned(2)));
+    static __device__ __forceinline__ v4f load(const T *p) { return __builtin_convertvector(*(const v4_u *)p, v4f); }
+    static __device__ __forceinline__ float load1(const T *p) { return (float)*p; }
+    static __device__ __forceinline__ void store(T *p, v4f o) { *(v4_u *)p = __builtin_convertvector(o, v4); }
+    static __device__ __forceinline__ void store1(T *p, float o) { *p = (T)o; }
+};
+
 __device__ __forceinline__ float lane_read(float v, int src)        // v of lane src (any lane if src is out of range)
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(4 * src, __builtin_bit_cast(int, v)));
@@ -31,8 +49,8 @@ __device__ __forceinline__ float lane_read(float v, int src)        // v of lane
 
 // PADDED: the windows slide over the row extended by pad_left elements in front (and more behind, lv in all)
 // under the boundary rule pad_mode; an element of the extended row is read from the row element the rule names.
-template <int OP, int NS, bool PADDED>
-__global__ __launch_bounds__(kThreads) void slide_long_kernel(const float *__restrict__ x, float *__restrict__ y, int len,
+template <int OP, int NS, bool PADDED, typename T>
+__global__ __launch_bounds__(kThreads) void slide_long_kernel(const T *__restrict__ x, T *__restrict__ y, int len,
                                                               int lo, int w, float scale, int tiles_per_row,
                                                               int64_t n_tiles, int64_t n_units, int pad_left, int pad_mode,
                                                               int lv)
@@ -46,27 +64,28 @@ __global__ __launch_bounds__(kThreads) void slide_long_kernel(const float *__res
     if (tile >= n_tiles) return;
     const int64_t r = tile / tiles_per_row;
     const int i0 = (int)(tile - r * tiles_per_row) * B;
-    const float *xr = x + r * (int64_t)len;
-    float *yr = y + r * (int64_t)lo;
+    using Q = Quad<T>;
+    const T *xr = x + r * (int64_t)len;
+    T *yr = y + r * (int64_t)lo;
     const v4f id4 = {O::id(), O::id(), O::id(), O::id()};
     // four elements at index p .. p + 3 of the (extended) row, the identity beyond it
     auto load4 = [&](int p) -> v4f {
         if (PADDED) {
             const int q = p - pad_left;              // index in the physical row
-            if (q >= 0 && q + 4 <= len) return *(const v4f_u *)(xr + q);
+            if (q >= 0 && q + 4 <= len) return Q::load(xr + q);
             float e[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int src = p + u < lv ? pad_src(p + u, len, pad_left, pad_mode) : -1;
-                e[u] = src >= 0 ? xr[src] : O::id();
+                e[u] = src >= 0 ? Q::load1(xr + src) : O::id();
             }
             return (v4f){e[0], e[1], e[2], e[3]};
         }
-        if (p + 4 <= len) return *(const v4f_u *)(xr + p);
+        if (p + 4 <= len) return Q::load(xr + p);
         v4f v = id4;
-        if (p < len) v.x = xr[p];
-        if (p + 1 < len) v.y = xr[p + 1];
-        if (p + 2 < len) v.z = xr[p + 2];
+        if (p < len) v.x = Q::load1(xr + p);
+        if (p + 1 < len) v.y = Q::load1(xr + p + 1);
+        if (p + 2 < len) v.z = Q::load1(xr + p + 2);
         return v;
     };
     v4f own[NS], end[NS];
@@ -155,17 +174,17 @@ __global__ __launch_bounds__(kThreads) void slide_long_kernel(const float *__res
         o.z = O::f(O::f(own[j].z, mid), end[j].z); o.w = O::f(O::f(own[j].w, mid), end[j].w);
         if (OP == SWS_OP_ADD) { o.x *= scale; o.y *= scale; o.z *= scale; o.w *= scale; }
         if (q + 4 <= lo) {
-            __builtin_nontemporal_store(o, (v4f_u *)(yr + q));
+            Q::store(yr + q, o);
         } else {
-            if (q < lo) yr[q] = o.x;
-            if (q + 1 < lo) yr[q + 1] = o.y;
-            if (q + 2 < lo) yr[q + 2] = o.z;
+            if (q < lo) Q::store1(yr + q, o.x);
+            if (q + 1 < lo) Q::store1(yr + q + 1, o.y);
+            if (q + 2 < lo) Q::store1(yr + q + 2, o.z);
         }
     }
 }
 
-template <int OP, int NS>
-hipError_t launch_long(const float *x, float *y, int64_t rows, int len, int lo, int w, float scale, bool padded,
+template <int OP, int NS, typename T>
+hipError_t launch_long(const T *x, T *y, int64_t rows, int len, int lo, int w, float scale, bool padded,
                        int pad_left, int pad_mode, int lv, hipStream_t s)
 {
     constexpr int B = 256 * NS;
@@ -175,10 +194,10 @@ hipError_t launch_long(const float *x, float *y, int64_t rows, int len, int lo, 
     const int64_t grid = xcd_grid(n_units);
     if (grid > 2147483647LL) return kNotTaken;
     if (padded)
-        hipLaunchKernelGGL((slide_long_kernel<OP, NS, true>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo, w,
+        hipLaunchKernelGGL((slide_long_kernel<OP, NS, true, T>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo, w,
                            scale, tiles_per_row, n_tiles, n_units, pad_left, pad_mode, lv);
     else
-        hipLaunchKernelGGL((slide_long_kernel<OP, NS, false>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo, w,
+        hipLaunchKernelGGL((slide_long_kernel<OP, NS, false, T>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo, w,
                            scale, tiles_per_row, n_tiles, n_units, 0, 0, len);
     return hipGetLastError();
 }
@@ -202,6 +221,28 @@ hipError_t launch_slide1d_long(int op, const float *x, float *y, int64_t rows, i
     if (w <= 1024) { SWS_LONG(2) }
     SWS_LONG(4)
 #undef SWS_LONG
+}
+
+// The same on 16-bit storage (dtype SWS_DTYPE_BF16 / SWS_DTYPE_F16; fp32 arithmetic, one rounding per output).
+hipError_t launch_slide1d_long_16(int op, int dtype, const void *x, void *y, int64_t rows, int len, int lo, int w,
+                                  float scale, hipStream_t s)
+{
+    if (w <= 256) return kNotTaken;
+#define SWS_LONG16(T_, NS_)                                                                                        \
+    switch (op) {                                                                                                  \
+    case SWS_OP_ADD: return launch_long<SWS_OP_ADD, NS_, T_>((const T_ *)x, (T_ *)y, rows, len, lo, w, scale, false, 0, 0, len, s); \
+    case SWS_OP_MAX: return launch_long<SWS_OP_MAX, NS_, T_>((const T_ *)x, (T_ *)y, rows, len, lo, w, scale, false, 0, 0, len, s); \
+    default: return launch_long<SWS_OP_MIN, NS_, T_>((const T_ *)x, (T_ *)y, rows, len, lo, w, scale, false, 0, 0, len, s);         \
+    }
+    if (dtype == SWS_DTYPE_BF16) {
+        if (w <= 512) { SWS_LONG16(__bf16, 1) }
+        if (w <= 1024) { SWS_LONG16(__bf16, 2) }
+        SWS_LONG16(__bf16, 4)
+    }
+    if (w <= 512) { SWS_LONG16(_Float16, 1) }
+    if (w <= 1024) { SWS_LONG16(_Float16, 2) }
+    SWS_LONG16(_Float16, 4)
+#undef SWS_LONG16
 }
 
 }  // namespace sws

@@ -117,6 +117,8 @@ hipError_t launch_slide1d_rows(int op, const float *x, float *y, int64_t rows, i
 // rule other than the shrinking window; kNotTaken otherwise.
 hipError_t launch_slide1d_long(int op, const float *x, float *y, int64_t rows, int len, int lo, int w, float scale,
                                bool padded, int pad_left, int pad_mode, int lv, hipStream_t s);
+hipError_t launch_slide1d_long_16(int op, int dtype, const void *x, void *y, int64_t rows, int len, int lo, int w,
+                                  float scale, hipStream_t s);
 hipError_t launch_slide1d_generic(int op, const float *x, float *y, int64_t rows, int64_t len, int32_t w, float scale,
                                   hipStream_t s);
 hipError_t launch_pool2d(int op, const float *x, float *y, int64_t planes, int64_t H, int64_t W,

@@ -181,3 +181,19 @@ def test_pool2d_16_argument_checks(B):
         B.sws_pool2d_16(0, x.float(), 3, 3)
     assert B.lib().sws_pool2d_16(0, 0, x.data_ptr(), x.data_ptr(), 1, 2, 8, 8, 3, 3, 1, 1, 1, 1, 1.0, None) == B.SWS_ERR_INVALID_ARG
     assert B.lib().sws_pool2d_16(0, 2, x.data_ptr(), x.data_ptr(), 1, 2, 8, 8, 3, 3, 1, 1, 3, 1, 1.0, None) == B.SWS_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("kind", ["bf16", "f16"])
+@pytest.mark.parametrize("op", ["add", "max", "min"])
+@pytest.mark.parametrize("w,length", [(257, 300), (512, 2000), (513, 5003), (962, 5003), (1024, 4097), (1025, 1025), (2048, 9001), (5000, 16384)])
+def test_windows_longer_than_a_tile_in_one_pass(B, kind, op, w, length):
+    """The long-window kernel on 16-bit storage (forced from w = 257 by slide_variant 8; the default from w = 962),
+    and direct evaluation (slide_variant 1) beside it."""
+    rng = np.random.Generator(np.random.PCG64(3000 + w + length))
+    x = (rng.random((3, length), dtype=np.float32) * 2 - 1).astype(np.float32)
+    for variant in (8, 0, 1):
+        B.sws_set_option("slide_variant", variant)
+        try:
+            _check(B, op, kind, x, w, scale=1.0 / w, what="%s %s w=%d variant %d" % (kind, op, w, variant))
+        finally:
+            B.sws_set_option("slide_variant", 0)
