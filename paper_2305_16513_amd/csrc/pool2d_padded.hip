@@ -165,14 +165,15 @@ __global__ __launch_bounds__(kThreads) void pool2d_padded_kernel(const float *__
 
 // ------------------------------------------------------------------------------------------------
 // The pooling layers' own shapes — 3 x 3 with one virtual column on the left (stride 1: and one on the
-// right), 2 x 2 stride 2 without virtual columns, rows of 4 .. 256 elements in multiples of 4 — without
+// right), 5 x 5 and 7 x 7 at stride 1 with two / three a side, 2 x 2 stride 2 without virtual columns, rows of
+// 4 .. 256 elements in multiples of 4 — without
 // LDS: a lane owns four adjacent columns, the W/4 lanes of a group hold one input row, the 64 / (W/4)
 // groups of a wavefront take consecutive bands of TH output rows.  A lane keeps the (TH-1)*S + K rows
 // of its band in registers (each read from the plane row the boundary rule names), forms the sum down
 // H on them, and takes the column beside its four from the neighbouring lane (DPP).  The rule acts on
 // rows and columns independently, so a virtual column of the row-reduced values is the reduced value
-// of the column it stands for: the second element of the same lane (mirror, left edge), its first
-// (repeated edge), or the last element of the group's last lane (periodic; one ds_bpermute) — and
+// of the column it stands for: elements of the same lane (mirror: columns 1 .. 3 for the left edge;
+// repeated edge: column 0), or elements of the group's last lane (periodic; one ds_bpermute each) — and
 // likewise on the right.  A workgroup is one short-lived wavefront; XCD x takes planes 8q + x.
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ float lane_before(float v)       // the value held by lane - 1
@@ -199,7 +200,7 @@ __global__ __launch_bounds__(kWave) void pool2d_padded_rows_kernel(const float *
     constexpr int NRT = (S == 1) ? K - 1 - PW : (K - 2 - PW > 0 ? K - 2 - PW : 0);   // ... from the lane after
     constexpr int NOUT = (S == 1) ? 4 : 2;                           // outputs per lane and row
     constexpr int NR = (TH - 1) * S + K;                             // rows of a band
-    static_assert(NL <= 1 && NRT <= 1, "one virtual column on a side");
+    static_assert(NL <= 3 && NRT <= 3, "the virtual columns of an edge lane are cells of that lane or of the group's other edge lane");
     const int lane = threadIdx.x;
     const int grp = (lane * lpr_rcp) >> 16, l = lane - grp * LPR;    // lane / LPR (exact for lane < 64)
     if (grp >= G) return;
@@ -228,17 +229,20 @@ __global__ __launch_bounds__(kWave) void pool2d_padded_rows_kernel(const float *
             v.z = O::f(v.z, r[i * S + a].z); v.w = O::f(v.w, r[i * S + a].w);
         }
         e[NL] = v.x; e[NL + 1] = v.y; e[NL + 2] = v.z; e[NL + 3] = v.w;
-        if constexpr (NL == 1) {
-            const float nb = lane_before(v.w);
-            float edge = mode == SWS_PAD_MIRROR ? v.y : v.x;
-            if (mode == SWS_PAD_PERIODIC) edge = from_lane(v.w, lane + LPR - 1);   // uniform branch: every lane takes part
-            e[0] = first ? edge : nb;
+        const float own[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int t = 0; t < NL; ++t) {                                   // column -(t + 1) of my four
+            const float nb = lane_before(own[3 - t]);
+            float edge = mode == SWS_PAD_MIRROR ? own[t + 1] : own[0];   // mirror: column t + 1; repeated edge: column 0
+            if (mode == SWS_PAD_PERIODIC) edge = from_lane(own[3 - t], lane + LPR - 1);   // uniform branch: every lane takes part
+            e[NL - 1 - t] = first ? edge : nb;
         }
-        if constexpr (NRT == 1) {
-            const float nb = lane_after(v.x);
-            float edge = mode == SWS_PAD_MIRROR ? v.z : v.w;
-            if (mode == SWS_PAD_PERIODIC) edge = from_lane(v.x, lane - LPR + 1);
-            e[NL + 4] = last ? edge : nb;
+#pragma unroll
+        for (int t = 0; t < NRT; ++t) {                                  // column 4 + t of my four
+            const float nb = lane_after(own[t]);
+            float edge = mode == SWS_PAD_MIRROR ? own[2 - t] : own[3];   // mirror: column W - 2 - t; repeated edge: W - 1
+            if (mode == SWS_PAD_PERIODIC) edge = from_lane(own[t], lane - LPR + 1);
+            e[NL + 4 + t] = last ? edge : nb;
         }
         float o[NOUT];
 #pragma unroll
@@ -285,6 +289,10 @@ hipError_t dispatch_padded_rows(const float *x, float *y, int64_t planes, int H,
     if (mode != SWS_PAD_MIRROR && mode != SWS_PAD_PERIODIC && mode != SWS_PAD_EDGE) return hipSuccess;
     if (kh == 3 && sh == 1 && pl == 1 && pr == 1)
         return launch_padded_rows<OP, 3, 1, 1, 2>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
+    if (kh == 5 && sh == 1 && pl == 2 && pr == 2)
+        return launch_padded_rows<OP, 5, 1, 2, 2>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
+    if (kh == 7 && sh == 1 && pl == 3 && pr == 3)
+        return launch_padded_rows<OP, 7, 1, 3, 2>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
     if (kh == 3 && sh == 2 && pl == 1 && Wo == W / 2)
         return launch_padded_rows<OP, 3, 2, 1, 1>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
     if (kh == 2 && sh == 2 && pl == 0 && Wo == W / 2)

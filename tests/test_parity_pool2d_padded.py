@@ -81,14 +81,15 @@ def test_planes_wider_than_a_slice_are_cut_into_column_tiles(B, mode, op, geom, 
 @pytest.mark.parametrize("mode", ["mirror", "periodic", "edge"])
 @pytest.mark.parametrize("W", [4, 8, 28, 60, 112, 200, 256])
 def test_row_streaming_kernel_shapes(B, mode, W):
-    """3 x 3 with one virtual column on a side and 2 x 2 stride 2 on rows of 4 .. 256 elements: several
-    groups per wavefront, bands that end inside a group, unequal virtual rows above and below."""
+    """3 x 3 (one virtual column a side), 5 x 5 (two), 7 x 7 (three) and 2 x 2 stride 2 on rows of 4 .. 256 elements:
+    several groups per wavefront, bands that end inside a group, unequal virtual rows above and below."""
     r = np.random.Generator(np.random.PCG64(W))
     for H in (5, 33, 57):
         x = r.standard_normal((2, 5, H, W), dtype=np.float32)
         xi = r.integers(-9, 10, size=(1, 9, H, W)).astype(np.float32)
         for kh, s, pads in ((3, 1, (1, 1, 1, 1)), (3, 1, (4, 1, 0, 1)), (3, 2, (1, 1, 1, 1)), (3, 2, (0, 1, 3, 0)),
-                            (2, 2, (0, 0, 0, 0)), (2, 2, (1, 0, 2, 1)), (2, 2, (3, 0, 0, 0))):
+                            (2, 2, (0, 0, 0, 0)), (2, 2, (1, 0, 2, 1)), (2, 2, (3, 0, 0, 0)),
+                            (5, 1, (2, 2, 2, 2)), (5, 1, (0, 2, 4, 2)), (7, 1, (3, 3, 3, 3)), (7, 1, (4, 3, 2, 3))):
             for op in (0, 1, 2):
                 _check(B, op, x, kh, kh, s, s, pads, MODES[mode], what="rows")
             y = to_host(B.sws_pool2d_padded(0, to_gpu(xi), kh, kh, s, s, pads, MODES[mode], 1.0))
