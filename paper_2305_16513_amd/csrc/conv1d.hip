@@ -572,6 +572,12 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
         else if (dense_ok && !(valu_ok && prefer_few(Cin, Cout, k, stride > 1))) variant = 3;
         else variant = few_ok ? 6 : (strided_ok ? 7 : 1);
     }
+    if (variant == 3 && g_opt.conv1d_variant == 0 && !wadj && stride == 1 && dilation == 1) {
+        // a few dozen channels: the split-operand kernel that streams the input straight from memory
+        bool taken_s = false;
+        const hipError_t e = launch_conv1d_split(x, wgt, y, B, Cin, L, Cout, Lo, k, pad, s, &taken_s);
+        if (taken_s || e != hipSuccess) return e;
+    }
     if (variant == 3) {
         // the dense contraction is the 2-D kernel on images of height 1
         bool taken_m = false;

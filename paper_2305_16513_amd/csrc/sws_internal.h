@@ -149,6 +149,10 @@ hipError_t launch_conv1d(const float *x, const float *wgt, float *y, int64_t B, 
 hipError_t launch_conv1d_padded(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin, int64_t L,
                                 int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad_left, int32_t pad_right,
                                 int32_t dilation, int32_t groups, int mode, hipStream_t s);
+// Dense 1-D layers of 32 / 64 input channels on the bf16 matrix cores with split fp32 operands (conv1d_split.hip);
+// *taken = false: not one of its shapes, nothing launched.
+hipError_t launch_conv1d_split(const float *x, const float *wgt, float *y, int64_t B, int64_t Cin, int64_t L, int64_t Cout,
+                               int64_t Lo, int32_t k, int32_t pad, hipStream_t s, bool *taken);
 // 16-bit storage (conv1d16.hip): x, y bf16 / fp16, taps fp32.
 hipError_t launch_conv1d_16(int dtype, const void *x, const float *wgt, void *y, int64_t B, int64_t Cin, int64_t L,
                             int64_t Cout, int64_t Lo, int32_t k, int32_t stride, int32_t pad, int32_t dilation,

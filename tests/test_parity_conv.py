@@ -456,3 +456,45 @@ def test_conv2d_more_than_2_to_the_32_elements(B):
     assert_within_tol(gw, ref, mag, "big conv2d grad-weight")
     del x, y
     torch.cuda.empty_cache()
+
+
+# Dense 1-D layers of 32 / 64 input channels: the split-operand kernel that streams the input from memory
+# (bf16 matrix cores, fp32 accuracy).  B, Cin, L, Cout, k, pad
+SPLIT_1D = [(2, 64, 500, 64, 3, 0), (3, 64, 1000, 96, 3, 1), (1, 32, 77, 32, 3, 2), (2, 32, 300, 160, 5, 2), (4, 64, 33, 32, 1, 0),
+            (1, 64, 5, 64, 3, 1), (16, 64, 4096, 64, 3, 0), (5, 64, 31, 64, 3, 40), (2, 32, 2000, 32, 5, 0), (300, 64, 40, 64, 3, 1)]
+
+
+@pytest.mark.parametrize("integer", [False, True])
+@pytest.mark.parametrize("case", SPLIT_1D)
+def test_conv1d_dense_split_operands(B, case, integer):
+    b, cin, length, cout, k, pad = case
+    if integer:
+        x = workloads.integer_valued((b, cin, length), -6, 6, 1)
+        w = workloads.integer_valued((cout, cin, k), -4, 4, 2)
+    else:
+        r = _rng(700 + cin + length + k)
+        x = r.standard_normal((b, cin, length), dtype=np.float32)
+        w = (r.standard_normal((cout, cin, k)) / np.sqrt(cin * k)).astype(np.float32)
+    ref, mag = oracle.conv1d(x, w, 1, pad, 1, 1)
+    y = to_host(B.sws_conv1d(to_gpu(x), to_gpu(w), 1, pad, 1, 1))
+    B.sws_set_option("conv1d_variant", 3)                        # the fp32-instruction tile kernel
+    try:
+        z = to_host(B.sws_conv1d(to_gpu(x), to_gpu(w), 1, pad, 1, 1))
+    finally:
+        B.sws_set_option("conv1d_variant", 0)
+    if integer:
+        assert np.array_equal(y.astype(np.float64), ref) and np.array_equal(z.astype(np.float64), ref), str(case)
+    else:
+        worst = assert_within_tol(y, ref, mag, "split conv1d %s" % (case,))
+        assert worst < 2e-6, (case, worst)                       # fp32 accuracy, not bf16's
+        assert_within_tol(z, ref, mag, "tile conv1d %s" % (case,))
+
+
+def test_conv1d_dense_split_operands_carry_every_bit(B):
+    """x = 1 + k 2^-23 against weights of +-1 that cancel the ones: what is left lives in the third bf16 piece."""
+    r = _rng(71)
+    x = (1.0 + r.integers(0, 128, size=(2, 64, 300)) * 2.0 ** -23).astype(np.float32)
+    w = np.where(r.integers(0, 2, size=(64, 64, 3)) > 0, 1.0, -1.0).astype(np.float32)
+    ref, mag = oracle.conv1d(x, w, 1, 1, 1, 1)
+    y = to_host(B.sws_conv1d(to_gpu(x), to_gpu(w), 1, 1, 1, 1))
+    assert_within_tol(y, ref, mag, "low bits", tol=2e-7)
