@@ -299,7 +299,8 @@ sws_status sws_conv1d_grad_weight(const float *x, const float *gy, float *gw, in
  * Accumulation is fp32 and the summation order is unspecified; every output is within
  * 1e-5 * sum|terms| of the exact sum.  On some layers (64 input channels, 3 x 3, stride 1) a product
  * x * w is evaluated as six exact products of bf16 pieces of the fp32 operands, which drops less than
- * 2^-23 of it; products of integers below 2^8 stay exact.
+ * 2^-23 of it; products of integers below 2^8 stay exact.  (The same holds for sws_conv1d on dense
+ * layers of 32 / 64 input channels.)
  * Errors: as sws_conv1d. */
 sws_status sws_conv2d(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin,
                       int64_t H, int64_t W, int64_t Cout, int32_t kh, int32_t kw,
@@ -330,7 +331,10 @@ sws_status sws_conv2d_padded(const float *x, const float *wgt, float *y, int64_t
  *   gw[co,ci,a,b]    = sum over (n, ho, wo) whose tap (a, b) lies inside the plane:
  *                      gy[n,co,ho,wo] * x[n,ci, ho*sh - ph + a, wo*sw - pw + b]
  * Sizes are those of the forward call.  gx and gw are overwritten; gw is summed with atomic adds
- * whose order is not fixed.
+ * whose order is not fixed.  Accuracy as for sws_conv2d; on some layers (3 x 3, stride 1 or 2, channel
+ * counts in multiples of 32) a product is evaluated as six exact products of bf16 pieces of its fp32
+ * operands, which drops less than 2^-23 of it (inputs must be finite there: an infinite operand splits
+ * into inf and NaN).
  *   gy : device [N,Cout,Ho,Wo]   wgt, gw : device [Cout,Cin,kh,kw]   x, gx : device [N,Cin,H,W]
  * Errors: as sws_conv2d. */
 sws_status sws_conv2d_grad_input(const float *gy, const float *wgt, float *gx, int64_t N,
