@@ -57,28 +57,27 @@ __global__ __launch_bounds__(kThreads) void conv1d_split_kernel(const float *__r
     const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int co0 = blockIdx.y * 64;
-    // ---- the weights of my 64 output channels — one contiguous range of the weight array, read coalesced — split
-    //      and laid out as operands (A[i = co][k = ci]: lane i + 32 (k / 8), element k % 8), one bf16 at a time
+    // ---- the weights of my 64 output channels (one contiguous range of the weight array), split and laid out as
+    //      operands (A[i = co][k = ci]: lane i + 32 (k / 8), element k % 8): a thread takes two neighbouring input
+    //      channels of one tap at a time, so that every LDS store is a whole register of two bf16
     {
-        unsigned short *w16 = (unsigned short *)wl;
+        unsigned *w32 = (unsigned *)wl;
         const float *wb = wgt + (int64_t)co0 * Cin * K;
         const int n_mine = (Cout - co0 < 64 ? Cout - co0 : 64) * Cin * K;
-        // element idx = (col * Cin + ci) * K + t of the range; a thread's elements are kThreads apart
-        constexpr int CK = Cin * K;
-        int col = threadIdx.x / CK, rem = threadIdx.x - col * CK;
-        for (int idx = threadIdx.x; idx < 64 * CK; idx += kThreads) {
-            const float v = idx < n_mine ? wb[idx] : 0.0f;
-            float p2, p3;
-            split3(v, p2, p3);
-            const int ci = rem / K, t = rem - ci * K;            // K is a compile-time constant
+        constexpr int PK = (Cin / 2) * K;            // pairs per output channel
+        for (int pidx = threadIdx.x; pidx < 64 * PK; pidx += kThreads) {
+            const int col = pidx / PK, rem = pidx - col * PK, cp = rem / K, t = rem - cp * K;
+            const int idx = (col * Cin + 2 * cp) * K + t;
+            const float v0 = idx < n_mine ? wb[idx] : 0.0f, v1 = idx < n_mine ? wb[idx + K] : 0.0f;
+            float a2, a3, b2, b3;
+            split3(v0, a2, a3);
+            split3(v1, b2, b3);
+            const int ci = 2 * cp;
             const int o = ((col >> 5) * NC + (ci >> 4)) * K + t, ln = (col & 31) + 32 * ((ci & 15) >> 3);
-            unsigned short *dst = w16 + ((o * 3) * 64 + ln) * 8 + (ci & 7);
-            dst[0] = (unsigned short)(__float_as_uint(v) >> 16);
-            dst[64 * 8] = (unsigned short)(__float_as_uint(p2) >> 16);
-            dst[2 * 64 * 8] = (unsigned short)(__float_as_uint(p3) >> 16);
-            rem += kThreads % CK;
-            col += kThreads / CK;
-            if (rem >= CK) { rem -= CK; ++col; }
+            unsigned *dst = w32 + ((o * 3) * 64 + ln) * 4 + ((ci & 7) >> 1);
+            dst[0] = pack_hi(v0, v1);
+            dst[64 * 4] = pack_hi(a2, b2);
+            dst[2 * 64 * 4] = pack_hi(a3, b3);
         }
     }
     __syncthreads();
