@@ -518,6 +518,24 @@ def run_only(torch, B, workloads, name, steps, cold=False):
         else:
             gw = torch.empty_like(w2)
             fn = lambda: B.sws_conv1d_grad_weight(x2, gy, 3, gw=gw)
+    elif name.startswith("gw2d_"):                        # gw2d_<n>x<cin>x<h>x<w>_<cout>_k<kh>x<kw>_p<ph>x<pw>: any stride-1 layer's grad-weight
+        _, shp, co, kk, pp = name.split("_")
+        n, ci, h, w = (int(v) for v in shp.split("x"))
+        kh, kw = (int(v) for v in kk[1:].split("x"))
+        ph, pw = (int(v) for v in pp[1:].split("x"))
+        xs = torch.empty(n, ci, h, w, device="cuda").normal_()
+        gs = torch.empty(n, int(co), h + 2 * ph - kh + 1, w + 2 * pw - kw + 1, device="cuda").normal_()
+        gws = torch.empty(int(co), ci, kh, kw, device="cuda")
+        fn = lambda: B.sws_conv2d_grad_weight(xs, gs, kh, kw, 1, 1, ph, pw, gw=gws)
+    elif name in ("grad_input_dense256", "grad_weight_dense256"):   # the 256 -> 256 channel 1-D layer of the adjoints table
+        xr = torch.empty(32, 256, 3136, device="cuda").normal_()
+        gr = torch.empty(32, 256, 3136, device="cuda").normal_()
+        if name.startswith("grad_input"):
+            wr = torch.empty(256, 256, 3, device="cuda").normal_()
+            fn = lambda: B.sws_conv1d_grad_input(gr, wr, 3136, 1, 1, gx=xr)
+        else:
+            gwr = torch.empty(256, 256, 3, device="cuda")
+            fn = lambda: B.sws_conv1d_grad_weight(xr, gr, 3, 1, 1, gw=gwr)
     elif name in ("grad_input_cfg4", "grad_weight_cfg4"):
         x4, w4 = workloads.make(4)
         x4, w4 = g(x4), g(w4)

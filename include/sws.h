@@ -280,7 +280,10 @@ sws_status sws_conv1d_16(sws_dtype dtype, const void *x, const float *wgt, void 
  *
  * All sizes are those of the forward call (L is the length of x, Lo = sws_out_len(...) that of
  * gy).  gx and gw are overwritten, not accumulated into.  gw is summed with atomic adds whose
- * order is not fixed: its last bits may differ between runs.
+ * order is not fixed: its last bits may differ between runs.  On dense layers (groups = 1, stride and
+ * dilation 1, k = 1, 3 or 5, channel counts in multiples of 32) a product of gw is evaluated as six
+ * exact products of bf16 pieces of its fp32 operands, which drops less than 2^-23 of it (inputs
+ * must be finite there: an infinite operand splits into inf and NaN).
  *   gy : device [B,Cout,Lo]   wgt, gw : device [Cout,Cin/groups,k]   x, gx : device [B,Cin,L]
  * Errors: as sws_conv1d. */
 sws_status sws_conv1d_grad_input(const float *gy, const float *wgt, float *gx, int64_t B,
@@ -331,8 +334,9 @@ sws_status sws_conv2d_padded(const float *x, const float *wgt, float *y, int64_t
  *   gw[co,ci,a,b]    = sum over (n, ho, wo) whose tap (a, b) lies inside the plane:
  *                      gy[n,co,ho,wo] * x[n,ci, ho*sh - ph + a, wo*sw - pw + b]
  * Sizes are those of the forward call.  gx and gw are overwritten; gw is summed with atomic adds
- * whose order is not fixed.  Accuracy as for sws_conv2d; on some layers (3 x 3, stride 1 or 2, channel
- * counts in multiples of 32) a product is evaluated as six exact products of bf16 pieces of its fp32
+ * whose order is not fixed.  Accuracy as for sws_conv2d; on some layers (3 x 3 at stride 1 or 2, and
+ * 1 x 1, 1 x 3, 1 x 5 at stride 1 without padding above and below, channel counts in multiples of 32)
+ * a product of gw is evaluated as six exact products of bf16 pieces of its fp32
  * operands, which drops less than 2^-23 of it (inputs must be finite there: an infinite operand splits
  * into inf and NaN).
  *   gy : device [N,Cout,Ho,Wo]   wgt, gw : device [Cout,Cin,kh,kw]   x, gx : device [N,Cin,H,W]

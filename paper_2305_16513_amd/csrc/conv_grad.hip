@@ -646,6 +646,15 @@ hipError_t launch_conv2d_grad_weight(const float *x, const float *gy, float *gw,
             const hipError_t es = launch_conv2d_gw_split(x, gy, gw, N, Cin, H, W, Cout, Ho, Wo, kh, kw, sh, sw, ph, pw, s, &taken_s);
             if (taken_s || es != hipSuccess) return es;
         }
+        if (kh == 1 && sh == 1 && sw == 1 && ph == 0) {
+            // kernels one row high: the rows of all images as rows of a 1-D problem; a 1 x 1 kernel does not see the rows
+            // either, and the plane is then one long row
+            bool taken_s = false;
+            const bool flat = kw == 1 && pw == 0;
+            const hipError_t es = flat ? launch_conv1d_gw_split(x, gy, gw, N, 1, Cin, H * W, Cout, Ho * Wo, 1, 0, H * W, Ho * Wo, s, &taken_s)
+                                       : launch_conv1d_gw_split(x, gy, gw, N * H, (int)H, Cin, W, Cout, Wo, kw, pw, H * W, Ho * Wo, s, &taken_s);
+            if (taken_s || es != hipSuccess) return es;
+        }
         GwGeom gm;
         gm.Cin = (int)Cin; gm.Cout = (int)Cout; gm.L = (int)W; gm.Lo = (int)Wo; gm.k = kw; gm.pad = pw; gm.dilation = 1;
         gm.H = (int)H; gm.Ho = (int)Ho; gm.kh = kh; gm.sh = sh; gm.ph = ph; gm.sw = sw; gm.x_cs = H * W; gm.gy_cs = Ho * Wo;
@@ -723,6 +732,11 @@ hipError_t launch_conv1d_grad_weight(const float *x, const float *gy, float *gw,
         default: break;
         }
 #undef SWS_TGW
+    }
+    if (dense_ok && stride == 1 && dilation == 1) {
+        bool taken_s = false;
+        const hipError_t es = launch_conv1d_gw_split(x, gy, gw, B, 1, Cin, L, Cout, Lo, k, pad, L, Lo, s, &taken_s);
+        if (taken_s || es != hipSuccess) return es;
     }
     if (dense_ok) {
         GwGeom gm;

@@ -24,6 +24,8 @@
 // is not fixed.
 #include "sws_internal.h"
 
+#include <atomic>
+
 namespace sws {
 
 namespace {
@@ -299,7 +301,374 @@ __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Kernels one row high (1 x KW: the 1-D convolution, and 1 x 1 layers with a plane taken as one long row).
+// The products run over positions, so a matrix operand is 8 consecutive positions of one channel — across a
+// wavefront that is 32 different rows of memory.  The workgroup therefore stages a chunk of 64 output positions
+// through LDS: every thread loads pairs of neighbouring positions along the rows (coalesced), splits them once
+// into three bf16 pieces and stores each pair as one register into a [piece][channel][pair] array whose rows are
+// 36 registers long (144 bytes: 128-bit reads of 16 consecutive channels fall into different banks).  The four
+// wavefronts (32 output x 32 input channels each) then read their operands from there: 8 positions are four
+// registers, and a tap at an odd offset takes the halves of neighbouring registers (one byte permute each).
+// The loads of the next chunk are in flight while the matrix instructions of this one run.
+//   rows: row r of x starts at x + (r / RH * Cin + ci) * x_cs + (r % RH) * L, of gy likewise with Cout, gy_cs,
+//   Lo (RH = rows per image: 1 for the 1-D convolution, H for 1 x KW kernels on planes).
+// ------------------------------------------------------------------------------------------------
+constexpr int kRowPairs = 36;                                    // registers per staged row: 72 positions >= 64 + KW - 1
+constexpr int kStage = 3 * 64 * kRowPairs;                       // registers per staged tensor
+constexpr int kRowLds = 2 * 2 * kStage * 4;                      // bytes: two buffers of (x, gy)
+
+// One phase of the row kernel's loop: the matrix products of the chunk staged in (xc, gc), and the splitting of the
+// loaded chunk (vx, vg; first output position p0) into the other buffer (xn, gn).  The splitting is written out in
+// slices between the groups of six matrix instructions (one group per tap and 16 positions), so that the vector
+// unit works on the next chunk while the matrix unit works on this one; issue_loads() refills (vx, vg) and is called
+// once they are split, a few groups before the end.  SH: the staged row starts one position early (an even
+// position: pairs loaded as one 64-bit access, PAIR); NA sets of accumulators take turns, so that a matrix
+// instruction seldom waits for the one before it.
+template <int KW, int SH, bool PAIR, int NA, int NX, int NG, class Loads>
+__device__ __forceinline__ void row_phase(const unsigned *__restrict__ xc, const unsigned *__restrict__ gc,
+                                          unsigned *__restrict__ xn, unsigned *__restrict__ gn, v16f (&acc)[NA][KW],
+                                          const float (&vx)[NX][2], const float (&vg)[NG][2], int p0, int pad, int L, int Lo,
+                                          const int (&xpr)[NX], int gpr, int tid, int wave, int l32, int half, Loads &&issue_loads)
+{
+    constexpr int ND = (KW + SH + 6) / 2 + 1;                    // registers that hold positions 0 .. KW + SH + 6 of a run
+    constexpr int G = 4 * KW;                                    // groups of matrix instructions
+    constexpr int GS = G - (KW == 1 ? 1 : (KW == 3 ? 3 : 4));    // the splitting is spread over the first GS of them
+    const unsigned *ga = gc + ((wave & 1) * 32 + l32) * kRowPairs + 4 * half;
+    const unsigned *xa = xc + ((wave >> 1) * 32 + l32) * kRowPairs + 4 * half;
+    // positions outside the row count as zero
+    auto stage_pair = [&](int q) {
+        if (q < NX) {
+            const int j = q;
+            const int o = p0 - pad - SH + 2 * xpr[j];
+            const bool in0 = (unsigned)o < (unsigned)L, in1 = PAIR ? in0 : (unsigned)(o + 1) < (unsigned)L;
+            const float v0 = in0 ? vx[j][0] : 0.0f, v1 = in1 ? vx[j][1] : 0.0f;
+            float a2, a3, b2, b3;
+            split3(v0, a2, a3);
+            split3(v1, b2, b3);
+            const int at = j * kThreads + tid;                    // = row * kRowPairs + pair
+            xn[at] = pack_hi(v0, v1);
+            xn[64 * kRowPairs + at] = pack_hi(a2, b2);
+            xn[2 * 64 * kRowPairs + at] = pack_hi(a3, b3);
+        } else {
+            const int j = q - NX;
+            const int o = p0 + 2 * gpr;
+            const bool in0 = o < Lo, in1 = PAIR ? in0 : o + 1 < Lo;
+            const float v0 = in0 ? vg[j][0] : 0.0f, v1 = in1 ? vg[j][1] : 0.0f;
+            float a2, a3, b2, b3;
+            split3(v0, a2, a3);
+            split3(v1, b2, b3);
+            const int at = (j * (kThreads / 32) + (tid >> 5)) * kRowPairs + gpr;
+            gn[at] = pack_hi(v0, v1);
+            gn[64 * kRowPairs + at] = pack_hi(a2, b2);
+            gn[2 * 64 * kRowPairs + at] = pack_hi(a3, b3);
+        }
+    };
+    // operands of 16 positions (8 per half-wavefront): read one step ahead of the matrix instructions that use them,
+    // so that the LDS latency passes behind the step before
+    v4u A[2][3];
+    unsigned d[2][3][ND];
+    auto read_operands = [&](int ks, v4u (&Ao)[3], unsigned (&dd)[3][ND]) {
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            Ao[p] = *reinterpret_cast<const v4u *>(ga + p * 64 * kRowPairs + 8 * ks);
+            const unsigned *src = xa + p * 64 * kRowPairs + 8 * ks;
+            const v4u q = *reinterpret_cast<const v4u *>(src);
+            dd[p][0] = q[0]; dd[p][1] = q[1]; dd[p][2] = q[2]; dd[p][3] = q[3];
+#pragma unroll
+            for (int e = 4; e < ND; ++e) dd[p][e] = src[e];
+        }
+    };
+    read_operands(0, A[0], d[0]);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        if (ks < 3) read_operands(ks + 1, A[(ks + 1) & 1], d[(ks + 1) & 1]);
+        __builtin_amdgcn_sched_barrier(0);                       // the reads above stay above
+        const int cur = ks & 1;
+        // registers, from here on: keeps the compiler from fetching a shifted run from LDS a second time
+#pragma unroll
+        for (int p = 0; p < 3; ++p)
+#pragma unroll
+            for (int e = 0; e < ND; ++e) asm volatile("" : "+v"(d[cur][p][e]));
+        const v8bf a1 = __builtin_bit_cast(v8bf, A[cur][0]), a2 = __builtin_bit_cast(v8bf, A[cur][1]), a3 = __builtin_bit_cast(v8bf, A[cur][2]);
+#pragma unroll
+        for (int b = 0; b < KW; ++b) {
+            v4u Bp[3];
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    Bp[p][i] = ((b + SH) & 1) ? __builtin_amdgcn_perm(d[cur][p][(b + SH) / 2 + i + 1], d[cur][p][(b + SH) / 2 + i], 0x05040302u)
+                                              : d[cur][p][(b + SH) / 2 + i];
+            const v8bf b1 = __builtin_bit_cast(v8bf, Bp[0]), b2 = __builtin_bit_cast(v8bf, Bp[1]), b3 = __builtin_bit_cast(v8bf, Bp[2]);
+            v16f cc = acc[ks % NA][b];                           // smallest products first
+            cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a3, b1, cc, 0, 0, 0);
+            cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, b2, cc, 0, 0, 0);
+            cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b3, cc, 0, 0, 0);
+            cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, b1, cc, 0, 0, 0);
+            cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b2, cc, 0, 0, 0);
+            cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, cc, 0, 0, 0);
+            acc[ks % NA][b] = cc;
+            // this group's slice of the splitting, issued behind its matrix instructions
+            const int g = ks * KW + b;
+#pragma unroll
+            for (int q = 0; q < NX + NG; ++q)
+                if (q * GS / (NX + NG) == g) stage_pair(q);
+            // the registers are free again: the next loads go out behind the last groups
+            if (g == GS - 1) issue_loads();
+        }
+    }
+}
+
+template <int KW, int SH, bool PAIR>
+__global__ __launch_bounds__(kThreads) void conv1d_gw_split_kernel(const float *__restrict__ x, const float *__restrict__ gy,
+                                                                   float *__restrict__ gw, int Cin, int L, int Cout, int Lo,
+                                                                   int pad, int RH, int64_t x_cs, int64_t gy_cs, int cpr,
+                                                                   int64_t n_chunks, int64_t chunks_per_wg, int ci_blocks)
+{
+    constexpr int T = KW;
+    constexpr int NX = 64 * kRowPairs / kThreads, NG = 64 * 32 / kThreads;      // pairs per thread: 9 of x, 8 of gy
+    constexpr int NA = KW == 1 ? 4 : (KW == 3 ? 2 : 1);          // sets of accumulators
+    static_assert(KW + SH + 63 <= 2 * kRowPairs && (KW & 1) && (PAIR || !SH), "a chunk's inputs fit the staged row");
+    static_assert(16 * (64 * T + 1) <= 4 * kStage, "the transposition of the results fits the staging buffers");
+    extern __shared__ __align__(16) unsigned lds[];              // [buffer][x, gy][piece][channel][pair]
+    float (*red)[64 * T + 1] = reinterpret_cast<float (*)[64 * T + 1]>(lds);
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int co_blk = (int)(blockIdx.y / ci_blocks), ci_blk = (int)(blockIdx.y - co_blk * ci_blocks);
+    const int co0 = co_blk * 64, ci0 = ci_blk * 64;
+    v16f acc[NA][T];
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][t][v] = 0.0f;
+    // my pairs of the staging: fixed rows and columns for the whole kernel (rows past the last channel are read
+    // from the last one: what is computed from them is not written)
+    unsigned xrow[NX], grow[NG];                                 // byte offsets of my rows from the block's first channel
+    int xpr[NX], gpr;
+#pragma unroll
+    for (int j = 0; j < NX; ++j) {
+        const int idx = j * kThreads + tid, r = idx / kRowPairs;
+        xpr[j] = idx - r * kRowPairs;
+        xrow[j] = (unsigned)(ci0 + r < Cin ? r : Cin - 1 - ci0) * (unsigned)x_cs * 4u;
+    }
+    gpr = tid & 31;
+#pragma unroll
+    for (int j = 0; j < NG; ++j) {
+        const int r = j * (kThreads / 32) + (tid >> 5);
+        grow[j] = (unsigned)(co0 + r < Cout ? r : Cout - 1 - co0) * (unsigned)gy_cs * 4u;
+    }
+    const int64_t C0 = blockIdx.x * chunks_per_wg;
+    const int64_t C1 = C0 + chunks_per_wg < n_chunks ? C0 + chunks_per_wg : n_chunks;
+    // the next chunk to load: (image, row inside the image, chunk inside the row), stepped without divisions
+    int64_t img;
+    int hr, cr;
+    {
+        const int64_t r = C0 / cpr;
+        cr = (int)(C0 - r * cpr);
+        img = r / RH;
+        hr = (int)(r - img * RH);
+    }
+    int64_t c_load = C0;
+    int cr_over = 0;
+    // two sets of load registers: a chunk is loaded during one phase of the loop and split during the next
+    float rx[2][NX][2], rg[2][NG][2];
+    int p0r[2] = {0, 0};                                         // first output position of the chunk in a set
+    auto load_chunk = [&](float (&vx)[NX][2], float (&vg)[NG][2], int &p0s) {   // every offset clamped into its row: no branch
+        const int p0 = cr * 64;
+        p0s = (cr + cr_over) * 64;
+        const char *xb = reinterpret_cast<const char *>(x + (img * Cin + ci0) * x_cs + (int64_t)hr * L);
+        const char *gb = reinterpret_cast<const char *>(gy + (img * Cout + co0) * gy_cs + (int64_t)hr * Lo);
+        auto at = [](const char *base, unsigned byte_off) { return *reinterpret_cast<const float *>(base + byte_off); };
+        auto at2 = [](const char *base, unsigned byte_off) { return *reinterpret_cast<const float2 *>(base + byte_off); };
+#pragma unroll
+        for (int j = 0; j < NX; ++j) {
+            const int o = p0 - pad - SH + 2 * xpr[j];
+            if constexpr (PAIR) {                                // even position, even row length: both inside or both outside
+                const float2 v = at2(xb, xrow[j] + 4u * (unsigned)(o < 0 ? 0 : (o >= L ? L - 2 : o)));
+                vx[j][0] = v.x;
+                vx[j][1] = v.y;
+            } else {
+                vx[j][0] = at(xb, xrow[j] + 4u * (unsigned)(o < 0 ? 0 : (o >= L ? L - 1 : o)));
+                vx[j][1] = at(xb, xrow[j] + 4u * (unsigned)(o + 1 < 0 ? 0 : (o + 1 >= L ? L - 1 : o + 1)));
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < NG; ++j) {
+            const int o = p0 + 2 * gpr;
+            if constexpr (PAIR) {
+                const float2 v = at2(gb, grow[j] + 4u * (unsigned)(o >= Lo ? Lo - 2 : o));
+                vg[j][0] = v.x;
+                vg[j][1] = v.y;
+            } else {
+                vg[j][0] = at(gb, grow[j] + 4u * (unsigned)(o >= Lo ? Lo - 1 : o));
+                vg[j][1] = at(gb, grow[j] + 4u * (unsigned)(o + 1 >= Lo ? Lo - 1 : o + 1));
+            }
+        }
+        // past the last chunk the last one is loaded again and taken as zeros: every phase issues the same number
+        // of loads, so the waits on them can be counted exactly
+        if (++c_load < C1) {
+            if (++cr == cpr) {
+                cr = 0;
+                if (++hr == RH) { hr = 0; ++img; }
+            }
+        } else {
+            cr_over = 1 << 23;                                    // splits into zeros: the positions lie outside every row
+        }
+    };
+    // split a loaded chunk (positions outside the row count as zero) into a staging buffer
+    auto stage = [&](const float (&vx)[NX][2], const float (&vg)[NG][2], int p0, unsigned *xl, unsigned *gl) {
+#pragma unroll
+        for (int j = 0; j < NX; ++j) {
+            const int o = p0 - pad - SH + 2 * xpr[j];
+            const float v0 = (unsigned)o < (unsigned)L ? vx[j][0] : 0.0f, v1 = (unsigned)(o + 1) < (unsigned)L ? vx[j][1] : 0.0f;
+            float a2, a3, b2, b3;
+            split3(v0, a2, a3);
+            split3(v1, b2, b3);
+            const int at = j * kThreads + tid;                    // = row * kRowPairs + pair
+            xl[at] = pack_hi(v0, v1);
+            xl[64 * kRowPairs + at] = pack_hi(a2, b2);
+            xl[2 * 64 * kRowPairs + at] = pack_hi(a3, b3);
+        }
+#pragma unroll
+        for (int j = 0; j < NG; ++j) {
+            const int o = p0 + 2 * gpr;
+            const float v0 = o < Lo ? vg[j][0] : 0.0f, v1 = o + 1 < Lo ? vg[j][1] : 0.0f;
+            float a2, a3, b2, b3;
+            split3(v0, a2, a3);
+            split3(v1, b2, b3);
+            const int at = (j * (kThreads / 32) + (tid >> 5)) * kRowPairs + gpr;
+            gl[at] = pack_hi(v0, v1);
+            gl[64 * kRowPairs + at] = pack_hi(a2, b2);
+            gl[2 * 64 * kRowPairs + at] = pack_hi(a3, b3);
+        }
+    };
+    unsigned *const xl0 = lds, *const gl0 = lds + kStage, *const xl1 = lds + 2 * kStage, *const gl1 = lds + 3 * kStage;
+    // A phase of the loop: the products of one chunk out of its buffer with the splitting of the next chunk into the
+    // other buffer in between, then the loads of the chunk after that into the registers just emptied.
+#define SWS_ROW_PHASE(XC_, GC_, XN_, GN_, SET_)                                                                  \
+    {                                                                                                             \
+        const int p0_ = p0r[SET_];                                                                                \
+        row_phase<KW, SH, PAIR, NA, NX, NG>(XC_, GC_, XN_, GN_, acc, rx[SET_], rg[SET_], p0_, pad, L, Lo, xpr, gpr, tid, wave, l32, half, \
+                              [&]() { load_chunk(rx[SET_], rg[SET_], p0r[SET_]); });                              \
+    }                                                                                                             \
+    __syncthreads()
+    load_chunk(rx[0], rg[0], p0r[0]);
+    load_chunk(rx[1], rg[1], p0r[1]);
+    stage(rx[0], rg[0], p0r[0], xl0, gl0);
+    load_chunk(rx[0], rg[0], p0r[0]);
+    __syncthreads();
+    // phases in pairs (one straight loop body, so that the compiler can count the loads in flight): a workgroup with
+    // an odd number of chunks runs its last phase on a buffer of zeros
+    for (int64_t c = C0; c < C1; c += 2) {
+        SWS_ROW_PHASE(xl0, gl0, xl1, gl1, 1);                    // chunk c; stages c + 1 (set 1), then loads c + 3 into it
+        SWS_ROW_PHASE(xl1, gl1, xl0, gl0, 0);                    // chunk c + 1; stages c + 2 (set 0), then loads c + 4
+    }
+#undef SWS_ROW_PHASE
+    // ---- out: a quarter of the block's rows at a time through LDS, so that consecutive lanes add to consecutive
+    // (input channel, tap) of gw
+#pragma unroll
+    for (int a = 1; a < NA; ++a)
+#pragma unroll
+        for (int t = 0; t < T; ++t) acc[0][t] += acc[a][t];
+    const int ci_n = Cin - ci0 < 64 ? Cin - ci0 : 64;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (q) __syncthreads();
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            if ((wave & 1) * 2 + g / 2 != q) continue;           // rows 8g .. 8g+7 of my block lie in quarter (wave&1)*2 + g/2
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int rl = 8 * (g & 1) + 4 * half + u;       // row inside the quarter
+#pragma unroll
+                for (int t = 0; t < T; ++t) red[rl][((wave >> 1) * 32 + l32) * T + t] = acc[0][t][4 * g + u];
+            }
+        }
+        __syncthreads();
+        constexpr int NE = 16 * 64 * T / kThreads;
+        float val[NE];
+#pragma unroll
+        for (int k = 0; k < NE; ++k) {
+            const int e = k * kThreads + tid, rl = e / (64 * T);
+            val[k] = red[rl][e - rl * (64 * T)];
+        }
+#pragma unroll
+        for (int k = 0; k < NE; ++k) {
+            const int e = k * kThreads + tid, rl = e / (64 * T), in = e - rl * (64 * T);
+            const int cc = co0 + 16 * q + rl;
+            if (cc < Cout && in < ci_n * T) atomicAdd(gw + ((int64_t)cc * Cin + ci0) * T + in, val[k]);
+        }
+    }
+}
+
 }  // namespace
+
+// Kernels one row high on dense channels (stride 1, channel counts in multiples of 32, k = 1, 3 or 5); rows: see the
+// kernel.  gw must hold zeros; *taken = false: not its case, nothing launched.
+hipError_t launch_conv1d_gw_split(const float *x, const float *gy, float *gw, int64_t rows, int RH, int64_t Cin, int64_t L,
+                                  int64_t Cout, int64_t Lo, int32_t k, int32_t pad, int64_t x_cs, int64_t gy_cs, hipStream_t s,
+                                  bool *taken)
+{
+    *taken = false;
+    if ((Cin & 31) || (Cout & 31) || rows < 1 || Lo < 1 || L < 1 || Cin > 32768 || Cout > 32768) return hipSuccess;
+    if (pad < 0 || pad > (1 << 20) || RH < 1) return hipSuccess;
+    if (64 * x_cs + L >= (1 << 30) || 64 * gy_cs + Lo >= (1 << 30)) return hipSuccess;       // 32-bit byte offsets inside a block
+    if (g_opt.conv2d_variant != 0 || g_opt.conv1d_variant != 0 || (k != 1 && k != 3 && k != 5)) return hipSuccess;
+    const int cpr = (int)((Lo + 63) / 64);                         // chunks of 64 output positions per row
+    const int64_t n_chunks = rows * cpr;
+    const int co_blocks = (int)((Cout + 63) / 64), ci_blocks = (int)((Cin + 63) / 64);
+    const int64_t blocks = (int64_t)co_blocks * ci_blocks;
+    if (blocks > 65535) return hipSuccess;
+    // Workgroups per block of gw: more of them shorten the walk over the chunks, and every one of them ends with
+    // 4096 k adds to memory, which the chip takes at about a third of a million per microsecond.  One workgroup
+    // fills a CU (LDS); a chunk takes it two microseconds or so (1.6 with the operands in the last-level cache, 3 from
+    // memory).
+    const int cus = device_cus();
+    int64_t best = 1;
+    double best_t = 1e30;
+    for (int64_t sgroups = 1; sgroups * blocks <= (int64_t)cus && sgroups <= n_chunks; ++sgroups) {
+        const double t = (double)((n_chunks + sgroups - 1) / sgroups) * 2.0 + (double)(sgroups * blocks) * 4096.0 * k / 350000.0;
+        if (t < best_t) { best_t = t; best = sgroups; }
+    }
+    int64_t wgs = best;
+    if (g_opt.slide_group > 0) wgs = g_opt.slide_group;
+    if (wgs > n_chunks) wgs = n_chunks;
+    const int64_t per = (n_chunks + wgs - 1) / wgs;
+    const int64_t grid = (n_chunks + per - 1) / per;
+    if (grid > 2147483647LL) return hipSuccess;
+    *taken = true;
+    // pairs of positions as one 64-bit access where every pair is aligned and lies wholly inside or outside its row
+    const bool pair = !((uintptr_t)x & 7) && !((uintptr_t)gy & 7) && !(x_cs & 1) && !(gy_cs & 1) && !(L & 1) && !(Lo & 1);
+    const int shift = pair ? (pad & 1) : 0;
+#define SWS_GW1(KW_, SH_, PAIR_)                                                                                   \
+    do {                                                                                                           \
+        static std::atomic<int> raised{0};                                                                         \
+        if (!raised.load(std::memory_order_relaxed)) {                                                             \
+            const hipError_t e = hipFuncSetAttribute((const void *)conv1d_gw_split_kernel<KW_, SH_, PAIR_>,        \
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kRowLds);         \
+            if (e != hipSuccess) return e;                                                                         \
+            raised.store(1, std::memory_order_relaxed);                                                            \
+        }                                                                                                          \
+        hipLaunchKernelGGL((conv1d_gw_split_kernel<KW_, SH_, PAIR_>), dim3((unsigned)grid, (unsigned)blocks), dim3(kThreads), \
+                           kRowLds, s, x, gy, gw, (int)Cin, (int)L, (int)Cout, (int)Lo, pad, RH, x_cs, gy_cs, cpr, n_chunks, per, \
+                           ci_blocks);                                                                             \
+    } while (0)
+#define SWS_GW1_K(KW_)                                                                                             \
+    do {                                                                                                           \
+        if (!pair) SWS_GW1(KW_, 0, false);                                                                         \
+        else if (shift) SWS_GW1(KW_, 1, true);                                                                     \
+        else SWS_GW1(KW_, 0, true);                                                                                \
+    } while (0)
+    if (k == 1) SWS_GW1_K(1);
+    else if (k == 3) SWS_GW1_K(3);
+    else SWS_GW1_K(5);
+#undef SWS_GW1_K
+#undef SWS_GW1
+    return hipGetLastError();
+}
 
 // *taken = false: not this kernel's case (nothing launched).  gw must hold zeros.
 hipError_t launch_conv2d_gw_split(const float *x, const float *gy, float *gw, int64_t N, int64_t Cin, int64_t H, int64_t W,

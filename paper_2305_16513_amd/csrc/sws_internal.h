@@ -185,6 +185,11 @@ hipError_t launch_conv2d_gw_split(const float *x, const float *gy, float *gw, in
                                   int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh, int32_t sw,
                                   int32_t ph, int32_t pw, hipStream_t s, bool *taken);
 
+// The same for kernels one row high (the 1-D convolution; 1 x k layers): rows = images * RH rows of L inputs / Lo outputs.
+hipError_t launch_conv1d_gw_split(const float *x, const float *gy, float *gw, int64_t rows, int RH, int64_t Cin, int64_t L,
+                                  int64_t Cout, int64_t Lo, int32_t k, int32_t pad, int64_t x_cs, int64_t gy_cs, hipStream_t s,
+                                  bool *taken);
+
 // Matrix-core convolution (conv_mfma.hip); *taken = false: shape not covered, nothing launched.
 hipError_t launch_conv2d_mfma(const float *x, const float *wgt, float *y, int64_t N, int64_t Cin, int64_t H,
                               int64_t W, int64_t Cout, int64_t Ho, int64_t Wo, int32_t kh, int32_t kw, int32_t sh,

@@ -377,3 +377,66 @@ def test_split_operand_grad_weight_carries_every_bit(B):
     gw = to_host(B.sws_conv2d_grad_weight(to_gpu(x), to_gpu(g), 3, 3, 1, 1, 1, 1))
     rw, mw = oracle.conv2d_grad_weight(x, g, 3, 3, 1, 1, 1, 1)
     assert_within_tol(gw, rw, mw, "low bits", tol=2e-7)
+
+
+# ---- kernels one row high on the split-operand matrix-core kernel that walks along the row
+# B, Cin, L, Cout, k, stride, pad, dilation, groups
+SPLIT_GW_1D = [(3, 64, 1000, 64, 3, 1, 1, 1, 1), (2, 32, 333, 96, 3, 1, 0, 1, 1), (5, 96, 47, 32, 5, 1, 2, 1, 1),
+               (2, 32, 16, 32, 1, 1, 0, 1, 1), (9, 160, 31, 32, 1, 1, 0, 1, 1), (40, 32, 5, 32, 3, 1, 1, 1, 1),
+               (1, 32, 2049, 64, 5, 1, 4, 1, 1), (2, 64, 100, 32, 3, 1, 5, 1, 1), (1, 32, 3, 32, 3, 1, 0, 1, 1),
+               # even row lengths: pairs of positions as one 64-bit load, staged from an even position (odd and even pads)
+               (2, 32, 200, 32, 3, 1, 0, 1, 1), (2, 32, 130, 64, 5, 1, 2, 1, 1), (3, 32, 66, 32, 5, 1, 1, 1, 1),
+               (2, 64, 64, 32, 1, 1, 0, 1, 1), (2, 32, 500, 32, 3, 1, 2, 1, 1), (1, 32, 2, 32, 1, 1, 0, 1, 1),
+               (5, 32, 192, 32, 3, 1, 1, 1, 1), (1, 96, 4100, 32, 3, 1, 1, 1, 1), (2, 32, 70, 32, 5, 1, 3, 1, 1)]
+# N, Cin, H, W, Cout, kh, kw, sh, sw, ph, pw: 1 x 1 layers (the plane as one row) and 1 x k layers (each image row a row)
+SPLIT_GW_ROWS_2D = [(2, 64, 14, 14, 32, 1, 1, 1, 1, 0, 0), (3, 32, 7, 9, 96, 1, 1, 1, 1, 0, 0), (2, 32, 12, 21, 64, 1, 3, 1, 1, 0, 1),
+                    (1, 64, 5, 40, 32, 1, 5, 1, 1, 0, 0), (4, 32, 6, 6, 32, 1, 3, 1, 1, 0, 2), (2, 32, 12, 20, 64, 1, 3, 1, 1, 0, 1),
+                    (3, 32, 8, 8, 32, 1, 1, 1, 1, 0, 0)]
+
+
+@pytest.mark.parametrize("integer", [False, True])
+@pytest.mark.parametrize("case", SPLIT_GW_1D)
+def test_split_operand_grad_weight_rows_1d(B, case, integer):
+    b, cin, length, cout, k, stride, pad, dil, groups = case
+    x, _, g = _data(case, 700 + cin + length, integer)
+    gw = to_host(B.sws_conv1d_grad_weight(to_gpu(x), to_gpu(g), k, stride, pad, dil, groups))
+    ref, mag = oracle.conv1d_grad_weight(x, g, k, stride, pad, dil, groups)
+    if integer:
+        assert np.array_equal(gw.astype(np.float64), ref), str(case)
+    else:
+        worst = assert_within_tol(gw, ref, mag, "split grad_weight %s" % (case,))
+        assert worst < 2e-6, (case, worst)                       # fp32 accuracy, not bf16's
+    B.sws_set_option("conv1d_variant", 3)                        # keeps the split-operand kernel out
+    try:
+        other = to_host(B.sws_conv1d_grad_weight(to_gpu(x), to_gpu(g), k, stride, pad, dil, groups))
+    finally:
+        B.sws_set_option("conv1d_variant", 0)
+    if integer:
+        assert np.array_equal(gw, other), str(case)
+    else:
+        assert_within_tol(other, ref, mag, "fp32-instruction grad_weight %s" % (case,))
+
+
+@pytest.mark.parametrize("integer", [False, True])
+@pytest.mark.parametrize("case", SPLIT_GW_ROWS_2D)
+def test_split_operand_grad_weight_rows_2d(B, case, integer):
+    n, cin, h, wd, cout, kh, kw, sh, sw, ph, pw = case
+    x, _, g = _data2d(case, 800 + cin + wd, integer)
+    gw = to_host(B.sws_conv2d_grad_weight(to_gpu(x), to_gpu(g), kh, kw, sh, sw, ph, pw))
+    rw, mw = oracle.conv2d_grad_weight(x, g, kh, kw, sh, sw, ph, pw)
+    if integer:
+        assert np.array_equal(gw.astype(np.float64), rw), str(case)
+    else:
+        worst = assert_within_tol(gw, rw, mw, "split grad_weight %s" % (case,))
+        assert worst < 2e-6, (case, worst)
+
+
+def test_split_operand_grad_weight_rows_carry_every_bit(B):
+    """x = 1 + k * 2^-23 against gradients of +-1: what survives the cancellation lives in the third bf16 piece."""
+    r = np.random.Generator(np.random.PCG64(62))
+    kx = r.integers(0, 128, size=(3, 32, 200))
+    x = (1.0 + kx * 2.0 ** -23).astype(np.float32)
+    g = np.where(r.integers(0, 2, size=(3, 32, 200)) > 0, 1.0, -1.0).astype(np.float32)
+    gw = to_host(B.sws_conv1d_grad_weight(to_gpu(x), to_gpu(g), 3, 1, 1, 1, 1))
+    ref, mag = oracle.conv1d_grad_weight(x, g, 3, 1, 1, 1, 1)
+    assert_within_tol(gw, ref, mag, "low bits", tol=2e-7)
