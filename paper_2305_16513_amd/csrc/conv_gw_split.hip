@@ -307,16 +307,22 @@ __global__ __launch_bounds__(kThreads) void conv2d_gw_split_kernel(const float *
 // wavefront that is 32 different rows of memory.  The workgroup therefore stages a chunk of 64 output positions
 // through LDS: every thread loads pairs of neighbouring positions along the rows (coalesced), splits them once
 // into three bf16 pieces and stores each pair as one register into a [piece][channel][pair] array whose rows are
-// 36 registers long (144 bytes: 128-bit reads of 16 consecutive channels fall into different banks).  The four
-// wavefronts (32 output x 32 input channels each) then read their operands from there: 8 positions are four
-// registers, and a tap at an odd offset takes the halves of neighbouring registers (one byte permute each).
-// The loads of the next chunk are in flight while the matrix instructions of this one run.
+// 36 registers long (144 bytes: 128-bit reads of 16 consecutive channels fall into different banks).  The eight
+// wavefronts (32 output x 32 input channels x one half of the chunk's positions each; two per SIMD, so that one's
+// waits pass behind the other's work) then read their operands from there: 8 positions are four registers, and
+// a tap at an odd offset takes the halves of neighbouring registers (one byte permute each).  Two staging buffers
+// and two sets of load registers: while the matrix instructions of chunk c run, chunk c + 1 is split into the
+// other buffer and the loads of chunk c + 3 go out.
 //   rows: row r of x starts at x + (r / RH * Cin + ci) * x_cs + (r % RH) * L, of gy likewise with Cout, gy_cs,
 //   Lo (RH = rows per image: 1 for the 1-D convolution, H for 1 x KW kernels on planes).
 // ------------------------------------------------------------------------------------------------
+constexpr int kRowThreads = 512;                                 // eight wavefronts: (output half, input half, half of a chunk's positions)
 constexpr int kRowPairs = 36;                                    // registers per staged row: 72 positions >= 64 + KW - 1
-constexpr int kStage = 3 * 64 * kRowPairs;                       // registers per staged tensor
-constexpr int kRowLds = 2 * 2 * kStage * 4;                      // bytes: two buffers of (x, gy)
+constexpr int kXRows = 72;                                       // staged rows of x: 64 channels, and 8 that only round the
+                                                                 // workgroup's share of pairs up to five per thread
+constexpr int kXPiece = kXRows * kRowPairs, kGPiece = 64 * kRowPairs;    // registers per bf16 piece
+constexpr int kStage = 3 * (kXPiece + kGPiece);                  // registers per staging buffer (x, then gy)
+constexpr int kRowLds = 2 * kStage * 4;                          // bytes: two buffers
 
 // One phase of the row kernel's loop: the matrix products of the chunk staged in (xc, gc), and the splitting of the
 // loaded chunk (vx, vg; first output position p0) into the other buffer (xn, gn).  The splitting is written out in
@@ -332,10 +338,11 @@ __device__ __forceinline__ void row_phase(const unsigned *__restrict__ xc, const
                                           const int (&xpr)[NX], int gpr, int tid, int wave, int l32, int half, Loads &&issue_loads)
 {
     constexpr int ND = (KW + SH + 6) / 2 + 1;                    // registers that hold positions 0 .. KW + SH + 6 of a run
-    constexpr int G = 4 * KW;                                    // groups of matrix instructions
-    constexpr int GS = G - (KW == 1 ? 1 : (KW == 3 ? 3 : 4));    // the splitting is spread over the first GS of them
-    const unsigned *ga = gc + ((wave & 1) * 32 + l32) * kRowPairs + 4 * half;
-    const unsigned *xa = xc + ((wave >> 1) * 32 + l32) * kRowPairs + 4 * half;
+    constexpr int G = 2 * KW;                                    // groups of matrix instructions (my half of the chunk)
+    constexpr int GS = G - (KW == 1 ? 1 : 2);                    // the splitting is spread over the first GS of them
+    const int kh = wave >> 2;                                    // my half of the chunk's positions
+    const unsigned *ga = gc + ((wave & 1) * 32 + l32) * kRowPairs + 4 * half + 16 * kh;
+    const unsigned *xa = xc + (((wave >> 1) & 1) * 32 + l32) * kRowPairs + 4 * half + 16 * kh;
     // positions outside the row count as zero
     auto stage_pair = [&](int q) {
         if (q < NX) {
@@ -346,10 +353,10 @@ __device__ __forceinline__ void row_phase(const unsigned *__restrict__ xc, const
             float a2, a3, b2, b3;
             split3(v0, a2, a3);
             split3(v1, b2, b3);
-            const int at = j * kThreads + tid;                    // = row * kRowPairs + pair
+            const int at = j * kRowThreads + tid;                 // = row * kRowPairs + pair
             xn[at] = pack_hi(v0, v1);
-            xn[64 * kRowPairs + at] = pack_hi(a2, b2);
-            xn[2 * 64 * kRowPairs + at] = pack_hi(a3, b3);
+            xn[kXPiece + at] = pack_hi(a2, b2);
+            xn[2 * kXPiece + at] = pack_hi(a3, b3);
         } else {
             const int j = q - NX;
             const int o = p0 + 2 * gpr;
@@ -358,10 +365,10 @@ __device__ __forceinline__ void row_phase(const unsigned *__restrict__ xc, const
             float a2, a3, b2, b3;
             split3(v0, a2, a3);
             split3(v1, b2, b3);
-            const int at = (j * (kThreads / 32) + (tid >> 5)) * kRowPairs + gpr;
+            const int at = (j * (kRowThreads / 32) + (tid >> 5)) * kRowPairs + gpr;
             gn[at] = pack_hi(v0, v1);
-            gn[64 * kRowPairs + at] = pack_hi(a2, b2);
-            gn[2 * 64 * kRowPairs + at] = pack_hi(a3, b3);
+            gn[kGPiece + at] = pack_hi(a2, b2);
+            gn[2 * kGPiece + at] = pack_hi(a3, b3);
         }
     };
     // operands of 16 positions (8 per half-wavefront): read one step ahead of the matrix instructions that use them,
@@ -371,8 +378,8 @@ __device__ __forceinline__ void row_phase(const unsigned *__restrict__ xc, const
     auto read_operands = [&](int ks, v4u (&Ao)[3], unsigned (&dd)[3][ND]) {
 #pragma unroll
         for (int p = 0; p < 3; ++p) {
-            Ao[p] = *reinterpret_cast<const v4u *>(ga + p * 64 * kRowPairs + 8 * ks);
-            const unsigned *src = xa + p * 64 * kRowPairs + 8 * ks;
+            Ao[p] = *reinterpret_cast<const v4u *>(ga + p * kGPiece + 8 * ks);
+            const unsigned *src = xa + p * kXPiece + 8 * ks;
             const v4u q = *reinterpret_cast<const v4u *>(src);
             dd[p][0] = q[0]; dd[p][1] = q[1]; dd[p][2] = q[2]; dd[p][3] = q[3];
 #pragma unroll
@@ -381,8 +388,8 @@ __device__ __forceinline__ void row_phase(const unsigned *__restrict__ xc, const
     };
     read_operands(0, A[0], d[0]);
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        if (ks < 3) read_operands(ks + 1, A[(ks + 1) & 1], d[(ks + 1) & 1]);
+    for (int ks = 0; ks < 2; ++ks) {
+        if (ks < 1) read_operands(ks + 1, A[(ks + 1) & 1], d[(ks + 1) & 1]);
         __builtin_amdgcn_sched_barrier(0);                       // the reads above stay above
         const int cur = ks & 1;
         // registers, from here on: keeps the compiler from fetching a shifted run from LDS a second time
@@ -421,16 +428,17 @@ __device__ __forceinline__ void row_phase(const unsigned *__restrict__ xc, const
 }
 
 template <int KW, int SH, bool PAIR>
-__global__ __launch_bounds__(kThreads) void conv1d_gw_split_kernel(const float *__restrict__ x, const float *__restrict__ gy,
+__global__ __launch_bounds__(kRowThreads) void conv1d_gw_split_kernel(const float *__restrict__ x, const float *__restrict__ gy,
                                                                    float *__restrict__ gw, int Cin, int L, int Cout, int Lo,
                                                                    int pad, int RH, int64_t x_cs, int64_t gy_cs, int cpr,
                                                                    int64_t n_chunks, int64_t chunks_per_wg, int ci_blocks)
 {
     constexpr int T = KW;
-    constexpr int NX = 64 * kRowPairs / kThreads, NG = 64 * 32 / kThreads;      // pairs per thread: 9 of x, 8 of gy
-    constexpr int NA = KW == 1 ? 4 : (KW == 3 ? 2 : 1);          // sets of accumulators
+    constexpr int NX = kXPiece / kRowThreads, NG = 64 * 32 / kRowThreads;       // pairs per thread: 5 of x, 4 of gy
+    static_assert(kXPiece >= NX * kRowThreads, "every thread's pairs lie inside the staged array");
+    constexpr int NA = KW == 5 ? 1 : 2;                          // sets of accumulators
     static_assert(KW + SH + 63 <= 2 * kRowPairs && (KW & 1) && (PAIR || !SH), "a chunk's inputs fit the staged row");
-    static_assert(16 * (64 * T + 1) <= 4 * kStage, "the transposition of the results fits the staging buffers");
+    static_assert(16 * (64 * T + 1) <= 2 * kStage, "the transposition of the results fits the staging buffers");
     extern __shared__ __align__(16) unsigned lds[];              // [buffer][x, gy][piece][channel][pair]
     float (*red)[64 * T + 1] = reinterpret_cast<float (*)[64 * T + 1]>(lds);
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
@@ -450,14 +458,15 @@ __global__ __launch_bounds__(kThreads) void conv1d_gw_split_kernel(const float *
     int xpr[NX], gpr;
 #pragma unroll
     for (int j = 0; j < NX; ++j) {
-        const int idx = j * kThreads + tid, r = idx / kRowPairs;
+        const int idx = j * kRowThreads + tid, r = idx / kRowPairs;
         xpr[j] = idx - r * kRowPairs;
-        xrow[j] = (unsigned)(ci0 + r < Cin ? r : Cin - 1 - ci0) * (unsigned)x_cs * 4u;
+        const int rr = r < 64 ? r : 63;                          // the rounding rows: loaded from a real one, never read
+        xrow[j] = (unsigned)(ci0 + rr < Cin ? rr : Cin - 1 - ci0) * (unsigned)x_cs * 4u;
     }
     gpr = tid & 31;
 #pragma unroll
     for (int j = 0; j < NG; ++j) {
-        const int r = j * (kThreads / 32) + (tid >> 5);
+        const int r = j * (kRowThreads / 32) + (tid >> 5);
         grow[j] = (unsigned)(co0 + r < Cout ? r : Cout - 1 - co0) * (unsigned)gy_cs * 4u;
     }
     const int64_t C0 = blockIdx.x * chunks_per_wg;
@@ -527,10 +536,10 @@ __global__ __launch_bounds__(kThreads) void conv1d_gw_split_kernel(const float *
             float a2, a3, b2, b3;
             split3(v0, a2, a3);
             split3(v1, b2, b3);
-            const int at = j * kThreads + tid;                    // = row * kRowPairs + pair
+            const int at = j * kRowThreads + tid;                 // = row * kRowPairs + pair
             xl[at] = pack_hi(v0, v1);
-            xl[64 * kRowPairs + at] = pack_hi(a2, b2);
-            xl[2 * 64 * kRowPairs + at] = pack_hi(a3, b3);
+            xl[kXPiece + at] = pack_hi(a2, b2);
+            xl[2 * kXPiece + at] = pack_hi(a3, b3);
         }
 #pragma unroll
         for (int j = 0; j < NG; ++j) {
@@ -539,13 +548,13 @@ __global__ __launch_bounds__(kThreads) void conv1d_gw_split_kernel(const float *
             float a2, a3, b2, b3;
             split3(v0, a2, a3);
             split3(v1, b2, b3);
-            const int at = (j * (kThreads / 32) + (tid >> 5)) * kRowPairs + gpr;
+            const int at = (j * (kRowThreads / 32) + (tid >> 5)) * kRowPairs + gpr;
             gl[at] = pack_hi(v0, v1);
-            gl[64 * kRowPairs + at] = pack_hi(a2, b2);
-            gl[2 * 64 * kRowPairs + at] = pack_hi(a3, b3);
+            gl[kGPiece + at] = pack_hi(a2, b2);
+            gl[2 * kGPiece + at] = pack_hi(a3, b3);
         }
     };
-    unsigned *const xl0 = lds, *const gl0 = lds + kStage, *const xl1 = lds + 2 * kStage, *const gl1 = lds + 3 * kStage;
+    unsigned *const xl0 = lds, *const gl0 = lds + 3 * kXPiece, *const xl1 = lds + kStage, *const gl1 = lds + kStage + 3 * kXPiece;
     // A phase of the loop: the products of one chunk out of its buffer with the splitting of the next chunk into the
     // other buffer in between, then the loads of the chunk after that into the registers just emptied.
 #define SWS_ROW_PHASE(XC_, GC_, XN_, GN_, SET_)                                                                  \
@@ -576,30 +585,38 @@ __global__ __launch_bounds__(kThreads) void conv1d_gw_split_kernel(const float *
     const int ci_n = Cin - ci0 < 64 ? Cin - ci0 : 64;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        if (q) __syncthreads();
+        // the wavefronts of the chunks' first halves write their quarter, those of the second halves add theirs
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            if ((wave & 1) * 2 + g / 2 != q) continue;           // rows 8g .. 8g+7 of my block lie in quarter (wave&1)*2 + g/2
+        for (int kh = 0; kh < 2; ++kh) {
+            if (q || kh) __syncthreads();
+            if ((wave >> 2) != kh) continue;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int rl = 8 * (g & 1) + 4 * half + u;       // row inside the quarter
+            for (int g = 0; g < 4; ++g) {
+                if ((wave & 1) * 2 + g / 2 != q) continue;       // rows 8g .. 8g+7 of my block lie in quarter (wave&1)*2 + g/2
 #pragma unroll
-                for (int t = 0; t < T; ++t) red[rl][((wave >> 1) * 32 + l32) * T + t] = acc[0][t][4 * g + u];
+                for (int u = 0; u < 4; ++u) {
+                    const int rl = 8 * (g & 1) + 4 * half + u;   // row inside the quarter
+#pragma unroll
+                    for (int t = 0; t < T; ++t) {
+                        float &cell = red[rl][(((wave >> 1) & 1) * 32 + l32) * T + t];
+                        cell = kh ? cell + acc[0][t][4 * g + u] : acc[0][t][4 * g + u];
+                    }
+                }
             }
         }
         __syncthreads();
-        constexpr int NE = 16 * 64 * T / kThreads;
+        constexpr int NE = (16 * 64 * T + kRowThreads - 1) / kRowThreads;
         float val[NE];
 #pragma unroll
         for (int k = 0; k < NE; ++k) {
-            const int e = k * kThreads + tid, rl = e / (64 * T);
-            val[k] = red[rl][e - rl * (64 * T)];
+            const int e = k * kRowThreads + tid, rl = e / (64 * T);
+            val[k] = e < 16 * 64 * T ? red[rl][e - rl * (64 * T)] : 0.0f;
         }
 #pragma unroll
         for (int k = 0; k < NE; ++k) {
-            const int e = k * kThreads + tid, rl = e / (64 * T), in = e - rl * (64 * T);
+            const int e = k * kRowThreads + tid, rl = e / (64 * T), in = e - rl * (64 * T);
             const int cc = co0 + 16 * q + rl;
-            if (cc < Cout && in < ci_n * T) atomicAdd(gw + ((int64_t)cc * Cin + ci0) * T + in, val[k]);
+            if (e < 16 * 64 * T && cc < Cout && in < ci_n * T) atomicAdd(gw + ((int64_t)cc * Cin + ci0) * T + in, val[k]);
         }
     }
 }
@@ -652,7 +669,7 @@ hipError_t launch_conv1d_gw_split(const float *x, const float *gy, float *gw, in
             if (e != hipSuccess) return e;                                                                         \
             raised.store(1, std::memory_order_relaxed);                                                            \
         }                                                                                                          \
-        hipLaunchKernelGGL((conv1d_gw_split_kernel<KW_, SH_, PAIR_>), dim3((unsigned)grid, (unsigned)blocks), dim3(kThreads), \
+        hipLaunchKernelGGL((conv1d_gw_split_kernel<KW_, SH_, PAIR_>), dim3((unsigned)grid, (unsigned)blocks), dim3(kRowThreads), \
                            kRowLds, s, x, gy, gw, (int)Cin, (int)L, (int)Cout, (int)Lo, pad, RH, x_cs, gy_cs, cpr, n_chunks, per, \
                            ci_blocks);                                                                             \
     } while (0)
