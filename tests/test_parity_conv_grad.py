@@ -440,3 +440,26 @@ def test_split_operand_grad_weight_rows_carry_every_bit(B):
     gw = to_host(B.sws_conv1d_grad_weight(to_gpu(x), to_gpu(g), 3, 1, 1, 1, 1))
     ref, mag = oracle.conv1d_grad_weight(x, g, 3, 1, 1, 1, 1)
     assert_within_tol(gw, ref, mag, "low bits", tol=2e-7)
+
+
+def test_split_operand_grad_weight_rows_at_full_size_on_sampled_channels(B):
+    """The layers bench.py times on this kernel, whole: the 256 -> 256 channel 1-D layer on [32,256,3136] (k = 3, pad 1)
+    and a 1 x 1 layer, 64 -> 256 channels on [32,64,56,56].  gw[co, ci, :] depends on channels co of gy and ci of x only,
+    so the oracle evaluates the sampled channel pairs from those channels' slices."""
+    r = np.random.Generator(np.random.PCG64(77))
+    x = r.standard_normal((32, 256, 3136), dtype=np.float32)
+    g = r.standard_normal((32, 256, 3136), dtype=np.float32)
+    gw = to_host(B.sws_conv1d_grad_weight(to_gpu(x), to_gpu(g), 3, 1, 1, 1, 1))
+    assert gw.shape == (256, 256, 3)
+    cos, cis = np.array([0, 31, 32, 63, 64, 130, 200, 255]), np.array([0, 1, 33, 62, 65, 127, 192, 255])
+    ref, mag = oracle.conv1d_grad_weight(np.ascontiguousarray(x[:, cis]), np.ascontiguousarray(g[:, cos]), 3, 1, 1, 1, 1)
+    worst = assert_within_tol(gw[np.ix_(cos, cis)], ref, mag, "256 -> 256 layer, sampled channel pairs")
+    assert worst < 2e-6, worst
+    del x, g
+    x2 = r.standard_normal((32, 64, 56, 56), dtype=np.float32)
+    g2 = r.standard_normal((32, 256, 56, 56), dtype=np.float32)
+    gw2 = to_host(B.sws_conv2d_grad_weight(to_gpu(x2), to_gpu(g2), 1, 1, 1, 1, 0, 0))
+    cis2 = np.array([0, 5, 31, 32, 40, 63])
+    ref2, mag2 = oracle.conv2d_grad_weight(np.ascontiguousarray(x2[:, cis2]), np.ascontiguousarray(g2[:, cos]), 1, 1, 1, 1, 0, 0)
+    worst = assert_within_tol(gw2[np.ix_(cos, cis2)], ref2, mag2, "1 x 1 layer, sampled channel pairs")
+    assert worst < 2e-6, worst
