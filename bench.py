@@ -815,14 +815,21 @@ def main():
             rec["GFLOPs"] = round(fl / ms / 1e6, 1)
         kernels[name] = rec
 
-    # dominant kernel: the one the step spends most time in (the six slide launches share
-    # one kernel template; the depthwise convolution is the other)
+    # dominant kernel: the one the step spends most time in.  The four launches with w = 64 and 255 run the scan
+    # kernel (slide_scan_kernel), the two with w = 16 the strips-in-registers kernel (slide_reg_kernel), the
+    # depthwise convolution the thin-channel kernel.
+    scan = [i for i, l in enumerate(launches[:6]) if not l[0].endswith("_w16")]
+    reg = [i for i, l in enumerate(launches[:6]) if l[0].endswith("_w16")]
+    for i, l in enumerate(launches):
+        kernels[l[0]]["kernel"] = "slide_scan_kernel" if i in scan else ("slide_reg_kernel" if i in reg else "conv1d_thin_kernel")
+    scan_ms = sum(per[i] for i in scan)
     slide_ms = sum(per[:6])
-    if slide_ms >= per[6]:
-        dom_name = "slide_scan_kernel (sws_slide1d, w in {16,64,255}, add and max)"
-        dom_bytes = sum(l[2] for l in launches[:6]) / 6.0
-        dom_ms = slide_ms / 6.0
-        traffic = read_traffic("slide_scan_cfg5_hbm_traffic.txt")
+    if scan_ms >= per[6] and scan_ms >= sum(per[i] for i in reg):
+        dom_name = "slide_scan_kernel (sws_slide1d, w in {64,255}, add and max)"
+        dom_bytes = sum(launches[i][2] for i in scan) / len(scan)
+        dom_ms = scan_ms / len(scan)
+        t64, t255 = read_traffic("slide_scan_cfg5_w64_hbm_traffic.txt"), read_traffic("slide_scan_cfg5_w255_hbm_traffic.txt")
+        traffic = (t64 + t255) / 2.0 if t64 and t255 else None
     else:
         dom_name = "depthwise conv kernel (sws_conv1d, k=31, groups=128)"
         dom_bytes = launches[6][2]

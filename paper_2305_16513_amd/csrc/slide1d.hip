@@ -567,6 +567,7 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
     if (variant == 4) return launch_slide1d_generic(op, x, y, rows, len64, w, scale, s);   // generic-operator kernel (A/B)
     if (variant == 7 && w > slide1d_rows_max_w()) variant = 0;
     if (variant == 8 && (w <= 256 || (padded && pad_mode == SWS_PAD_SHRINK))) variant = 0;   // the long-window kernel: w > 256
+    if (variant == 9 && (padded || w < slide1d_reg_min_w() || w > slide1d_reg_max_w())) variant = 0;   // strips in registers: plain rows
     // Measured on 16384-long rows: the scan kernel's tiles are more and more halo as w grows; from w = 449 the
     // long-window kernel takes over, beyond its reach a chain of shorter windows.
     if (variant == 0) {
@@ -598,6 +599,10 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
         else if (padded && pad_mode == SWS_PAD_SHRINK) variant = w <= kScanMaxW ? 3 : 1;   // one pass rescales by the real elements
         else if (padded) variant = w < kLongMinW ? 3 : (w <= kLongMaxW ? 8 : 6);   // 6: a chain over extended rows
         else if (small_w) variant = 2;
+        // Windows 12 .. 17 on large inputs: one strip per wavefront held in registers (strips overlap by 16 elements).
+        // Measured on x[32768,16384], ms per 2 GiB, that kernel / the scan: max 0.700-0.711 / 0.738, + 0.699-0.703 /
+        // 0.710-0.715; from w = 18 the overlap is 32 elements and + loses (0.73 / 0.714), max gains under 1.5 %.
+        else if (w >= 12 && w <= 17 && rows * (int64_t)lo >= (1LL << 24)) variant = 9;
         else variant = w < kLongMinW ? 3 : (w <= kLongMaxW ? 8 : 5);
     }
     if (variant == 8) {
@@ -619,6 +624,11 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
         case SWS_OP_MAX: return launch_chain_padded<SWS_OP_MAX>(x, y, rows, len, lo, w, pad_left, pad_mode, scale, s);
         default: return launch_chain_padded<SWS_OP_MIN>(x, y, rows, len, lo, w, pad_left, pad_mode, scale, s);
         }
+    }
+    if (variant == 9) {
+        const hipError_t e = launch_slide1d_reg(op, x, y, rows, len, lo, w, scale, s);
+        if (e != kNotTaken) return e;
+        variant = 3;
     }
     if (variant == 7) {
         const hipError_t e = launch_slide1d_rows(op, x, y, rows, len, lo, w, scale, padded, pad_left, pad_mode, s);

@@ -103,6 +103,14 @@ hipError_t launch_slide1d_16(int op, int dtype, const void *x, void *y, int64_t 
 // Generic-operator kernels (slide_generic.hip): the pair operator, and +, max, min as a cross-check.
 hipError_t launch_slide1d_pair(const float *u, const float *v, float *yu, float *yv, int64_t rows, int64_t len,
                                int32_t w, hipStream_t s);
+// Medium windows (slide1d_reg_min_w() .. slide1d_reg_max_w()) on plain rows: one 256-element strip per
+// single-wavefront workgroup, held in registers, whole lanes summed across the wavefront (slide_reg.hip).
+// kNotTaken: not its case, nothing launched.
+int slide1d_reg_min_w();
+int slide1d_reg_max_w();
+hipError_t launch_slide1d_reg(int op, const float *x, float *y, int64_t rows, int len, int lo, int w, float scale,
+                              hipStream_t s);
+
 // Short rows, windows up to slide1d_rows_max_w(): four outputs per lane from shifted 128-bit loads,
 // several rows per wavefront.  hipErrorInvalidValue: not taken (w or grid beyond its reach).
 // 2-D pooling on planes of a few hundred elements: several whole planes per workgroup through LDS.

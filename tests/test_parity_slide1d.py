@@ -412,3 +412,51 @@ def test_short_row_kernel(B, w, variant):
     finally:
         B.sws_set_option("slide_variant", 0)
 
+
+
+@pytest.mark.parametrize("w", [5, 6, 7, 8, 9, 12, 13, 15, 16, 17, 18, 20, 31, 32, 33, 34, 35, 48, 49, 62, 63, 64, 65])
+def test_strips_in_registers_kernel(B, w):
+    """Windows 5 .. 65 on one 256-element strip per wavefront, whole lanes summed across the wavefront (option
+    slide_variant 9 forces the kernel on every shape): several strips per row and ragged ends, rows shorter than a
+    strip, x and y off the 16-byte boundaries, the elements around y untouched."""
+    import torch
+    B.sws_set_option("slide_variant", 9)
+    try:
+        for rows, length in ((3, 5003), (7, 700), (40, 260), (9, 255 + w), (9, 256 + w), (300, 65), (5, 1031), (2, w),
+                             (130, 224), (1, 4099)):
+            if w > length:
+                continue
+            lo = length - w + 1
+            r = np.random.Generator(np.random.PCG64(w * 991 + length))
+            x = (r.random((rows, length), dtype=np.float32) * 2 - 1).astype(np.float32)
+            xbuf = torch.zeros(rows * length + 8, device="cuda")
+            xs = xbuf[1:1 + rows * length].view(rows, length)
+            xs.copy_(torch.from_numpy(x))
+            for op in (0, 1, 2):
+                ybuf = torch.full((rows * lo + 8,), 7.0, device="cuda")
+                ys = ybuf[3:3 + rows * lo].view(rows, lo)
+                B.sws_slide1d(op, xs, w, 0.5, y=ys)
+                y = to_host(ys)
+                ref, mag = oracle.slide1d(op, x, w, 0.5)
+                what = "w %d rows %d len %d op %d" % (w, rows, length, op)
+                if op == 0:
+                    assert_within_tol(y, ref, mag, what)
+                else:
+                    assert_bit_exact(y, ref, what)
+                guard = ybuf.cpu()
+                assert (guard[:3] == 7.0).all() and (guard[3 + rows * lo:] == 7.0).all(), what
+    finally:
+        B.sws_set_option("slide_variant", 0)
+
+
+def test_strips_in_registers_kernel_is_exact_on_integers(B):
+    """Small integers: every order of summation gives the same fp32 result, so + must agree bit for bit too."""
+    B.sws_set_option("slide_variant", 9)
+    try:
+        for w in (16, 23, 64):
+            x = workloads.integer_valued((33, 3000), -8, 8, 5 + w)
+            y = to_host(B.sws_slide1d(0, to_gpu(x), w, 1.0))
+            ref, _ = oracle.slide1d(0, x, w, 1.0)
+            assert_bit_exact(y, ref, "w %d" % w)
+    finally:
+        B.sws_set_option("slide_variant", 0)
