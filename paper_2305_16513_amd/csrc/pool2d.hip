@@ -579,6 +579,92 @@ hipError_t launch_rows(const T *x, T *y, int64_t planes, int H, int W, int Ho, i
     return hipGetLastError();
 }
 
+// The same kernel for planes wider than a wavefront's 256 columns: a wavefront takes a strip of 256 input columns
+// of its band, of which the two lanes at either end only serve their neighbours — strips overlap by 16 columns,
+// a strip yields 240 columns of outputs (stride 2: 120) and its stores are whole 64-byte lines (32-bit elements).
+// Columns outside the plane hold the identity, like rows outside it.  The strips of a band are neighbours in
+// launch order and run on one XCD, so the overlap is read from the L2 that fetched it.
+constexpr int kStripCols = 240, kStripHalo = 8;
+
+template <int OP, int K, int S, int PW, int TH, typename T>
+__global__ __launch_bounds__(kWave) void pool2d_rows_wide_kernel(const T *__restrict__ x, T *__restrict__ y, int H, int W,
+                                                                 int Ho, int Wo, int ph, int nstrips, int64_t planes,
+                                                                 float scale)
+{
+    using O = Op<OP>;
+    using IO = Io<T>;
+    constexpr int NL = PW;
+    constexpr int NRT = (S == 1) ? K - 1 - PW : (K - 2 - PW > 0 ? K - 2 - PW : 0);
+    constexpr int NOUT = (S == 1) ? 4 : 2;
+    constexpr int NR = (TH - 1) * S + K;
+    static_assert(NL <= 4 && NRT <= 4, "windows reach the immediate neighbour lanes only");
+    const int lane = threadIdx.x;
+    const int sl = (int)(blockIdx.x >> 3);                          // (band, strip) of the plane
+    const int64_t plane = (int64_t)blockIdx.y * kXcd + (blockIdx.x & 7);
+    if (plane >= planes) return;
+    const int band = sl / nstrips, strip = sl - band * nstrips;
+    const int ho0 = band * TH;
+    if (ho0 >= Ho) return;
+    const int c = strip * kStripCols - kStripHalo + 4 * lane;       // my four columns (a multiple of 4: wholly in or out)
+    const bool in_cols = c >= 0 && c < W;
+    const T *xp = x + plane * (int64_t)H * W + (in_cols ? c : 0);
+    const v4f id4 = {O::id(), O::id(), O::id(), O::id()};
+    v4f r[NR];
+#pragma unroll
+    for (int j = 0; j < NR; ++j) {                                   // all loads in flight together
+        const int row = ho0 * S - ph + j;
+        const bool ok = row >= 0 && row < H;
+        const v4f v = IO::load4(xp + (int64_t)(ok ? row : 0) * W);
+        r[j] = (ok && in_cols) ? v : id4;
+    }
+    const bool mine = lane >= kStripHalo / 4 && lane < kWave - kStripHalo / 4 && in_cols;
+    T *yp = y + plane * (int64_t)Ho * Wo + (S == 1 ? c : c / 2);
+#pragma unroll
+    for (int i = 0; i < TH; ++i) {
+        float e[NL + 4 + NRT];
+        v4f v = r[i * S];
+#pragma unroll
+        for (int a = 1; a < K; ++a) {
+            v.x = O::f(v.x, r[i * S + a].x); v.y = O::f(v.y, r[i * S + a].y);
+            v.z = O::f(v.z, r[i * S + a].z); v.w = O::f(v.w, r[i * S + a].w);
+        }
+        e[NL] = v.x; e[NL + 1] = v.y; e[NL + 2] = v.z; e[NL + 3] = v.w;
+        // (the lanes that store have both neighbours inside the wavefront, holding real columns or the identity)
+#pragma unroll
+        for (int t = 0; t < NL; ++t) e[NL - 1 - t] = lane_before(e[NL + 3 - t]);
+#pragma unroll
+        for (int t = 0; t < NRT; ++t) e[NL + 4 + t] = lane_after(e[NL + t]);
+        float o[NOUT];
+#pragma unroll
+        for (int cc = 0; cc < NOUT; ++cc) {
+            float acc = e[cc * S];
+#pragma unroll
+            for (int b = 1; b < K; ++b) acc = O::f(acc, e[cc * S + b]);
+            o[cc] = (OP == SWS_OP_ADD) ? acc * scale : acc;
+        }
+        const int ho = ho0 + i;
+        if (mine && ho < Ho) {
+            if constexpr (NOUT == 4) IO::store4(yp + (int64_t)ho * Wo, (v4f){o[0], o[1], o[2], o[3]}, false);
+            else IO::store2_nt(yp + (int64_t)ho * Wo, (v2f){o[0], o[1]});
+        }
+    }
+}
+
+template <int OP, int K, int S, int PW, int TH, typename T>
+hipError_t launch_rows_wide(const T *x, T *y, int64_t planes, int H, int W, int Ho, int Wo, int ph, float scale,
+                            hipStream_t s, bool *taken)
+{
+    const int nstrips = (W + kStripCols - 1) / kStripCols;
+    const int bands = (Ho + TH - 1) / TH;
+    const int64_t spp = (int64_t)bands * nstrips;                    // wavefronts per plane
+    const int64_t rounds = (planes + kXcd - 1) / kXcd;
+    *taken = rounds <= 65535 && spp * kXcd <= 2147483647LL;
+    if (!*taken) return hipSuccess;
+    hipLaunchKernelGGL((pool2d_rows_wide_kernel<OP, K, S, PW, TH, T>), dim3((unsigned)(spp * kXcd), (unsigned)rounds), dim3(kWave),
+                       0, s, x, y, H, W, Ho, Wo, ph, nstrips, planes, scale);
+    return hipGetLastError();
+}
+
 // The geometries the row-streaming kernel is built for: 3 x 3 with one column of padding at stride 1
 // and 2, 2 x 2 stride 2 without padding; rows of 4 .. 256 elements in multiples of 4; every output
 // divided by the same number.  Band heights as measured on [2048, 112, 112] under rotating buffers:
@@ -589,9 +675,17 @@ hipError_t dispatch_rows(const T *x, T *y, int64_t planes, int H, int W, int Ho,
                          int sw, int ph, int pw, float scale, int div_valid, hipStream_t s, bool *taken)
 {
     *taken = false;
-    if (div_valid || kh != kw || sh != sw || (W & 3) || W < 4 || W > 256 || ph < 0 || ph >= kh ||
-        (g_opt.pool2d_variant & 128))
+    if (div_valid || kh != kw || sh != sw || (W & 3) || W < 4 || ph < 0 || ph >= kh || (g_opt.pool2d_variant & 128))
         return hipSuccess;
+    if (W > 256) {                                   // strips of 256 columns
+        if (kh == 3 && sh == 1 && pw == 1 && Wo == W)
+            return launch_rows_wide<OP, 3, 1, 1, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+        // (measured on [128, 512, 512], cold, strips / band kernel: 3 x 3 stride 1 50 / 95 us, 2 x 2 stride 2 27.8 / 29.2 us,
+        // 3 x 3 stride 2 29.5 / 28.8 us — the last stays on the band kernel)
+        if (kh == 2 && sh == 2 && pw == 0 && Wo == W / 2)
+            return launch_rows_wide<OP, 2, 2, 0, 1, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+        return hipSuccess;
+    }
     if (kh == 3 && sh == 1 && pw == 1 && Wo == W)
         return launch_rows<OP, 3, 1, 1, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
     if (kh == 3 && sh == 2 && pw == 1 && Wo == W / 2)

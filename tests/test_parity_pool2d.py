@@ -306,3 +306,41 @@ def test_small_planes_four_sided_padding_and_real_cell_average(B, divisor, geom,
         else:
             assert_bit_exact(y, ref, "small pool2d_ex %s %s op=%d" % (shape, geom, op))
 
+
+
+@pytest.mark.parametrize("op", ["add", "max", "min"])
+@pytest.mark.parametrize("geom", [(3, 1, 1), (3, 2, 1), (2, 2, 0)])
+@pytest.mark.parametrize("shape", [(2, 3, 37, 260), (1, 2, 20, 512), (1, 1, 9, 1000), (9, 1, 6, 480), (1, 2, 11, 244 + 240)])
+def test_row_streaming_kernel_on_strips_of_wide_planes(B, op, geom, shape):
+    """The same windows on planes wider than 256 columns: strips of 256 input columns whose end lanes only serve
+    their neighbours (strip boundaries at multiples of 240, planes that end inside a strip or exactly on one, nine
+    planes = a second round of eight).  Against the oracle and against the band kernel (option pool2d_variant 128);
+    guard elements around y keep their value."""
+    import torch
+    k, s, p = geom
+    n, c, h, w = shape
+    rng = np.random.Generator(np.random.PCG64(2000 * k + 100 * s + h * w + n))
+    x = rng.standard_normal(shape, dtype=np.float32)
+    scale = 1.0 / (k * k)
+    for ph in sorted({p, 0, k - 1}):
+        ho, wo = (h + 2 * ph - k) // s + 1, (w + 2 * p - k) // s + 1
+        buf = torch.full((n * c * ho * wo + 64,), 4321.0, device="cuda")
+        yv = buf[32:32 + n * c * ho * wo].view(n, c, ho, wo)
+        B.sws_pool2d(OPS[op], to_gpu(x), k, k, s, s, ph, p, scale, y=yv)
+        y = to_host(yv)
+        ref, mag = oracle.pool2d(OPS[op], x, k, k, s, s, ph, p, scale)
+        what = "wide rows kernel %s %s ph=%d %s" % (op, geom, ph, shape)
+        if op == "add":
+            assert_within_tol(y, ref, mag, what)
+        else:
+            assert_bit_exact(y, ref, what)
+        assert bool((buf[:32] == 4321.0).all()) and bool((buf[32 + n * c * ho * wo:] == 4321.0).all()), what
+        B.sws_set_option("pool2d_variant", 128)
+        try:
+            other = to_host(B.sws_pool2d(OPS[op], to_gpu(x), k, k, s, s, ph, p, scale))
+        finally:
+            B.sws_set_option("pool2d_variant", 0)
+        if op == "add":
+            assert_within_tol(other, ref, mag, what + " (band kernel)")
+        else:
+            assert np.array_equal(y, other), what
