@@ -640,6 +640,14 @@ def run_only(torch, B, workloads, name, steps, cold=False):
         y = torch.empty(32, 64, ho, ho, device="cuda")
         op = 1 if opn == "max" else 0
         fn = rotating(x3, y)(lambda xx, yy: B.sws_pool2d_padded(op, xx, k, k, st, st, (k // 2,) * 4, mode, 1.0 / (k * k), y=yy))
+    elif name.startswith("widepad_"):                     # widepad_<avg|max>_<mirror|periodic|edge>_k<k>: x[8,16,512,512], stride 1, pad k // 2
+        _, opn, mn, kn = name.split("_")
+        k = int(kn[1:])
+        mode = {"mirror": B.SWS_PAD_MIRROR, "periodic": B.SWS_PAD_PERIODIC, "edge": B.SWS_PAD_EDGE}[mn]
+        xw = torch.empty(8, 16, 512, 512, device="cuda").uniform_(-1, 1)
+        y = torch.empty(8, 16, 512, 512, device="cuda")
+        op = 1 if opn == "max" else 0
+        fn = rotating(xw, y)(lambda xx, yy: B.sws_pool2d_padded(op, xx, k, k, 1, 1, (k // 2,) * 4, mode, 1.0 / (k * k), y=yy))
     elif name.startswith("wide_"):                        # wide_<avg|max>_k<k>_s<s>: x[8,16,512,512], pad k // 2 (k = 3) or 0 (k = 2)
         _, opn, kn, sn = name.split("_")
         k, st = int(kn[1:]), int(sn[1:])

@@ -278,6 +278,104 @@ hipError_t launch_padded_rows(const float *x, float *y, int64_t planes, int H, i
     return hipGetLastError();
 }
 
+// The same kernel for planes wider than a wavefront's 256 columns.  A wavefront takes a strip of 256 columns of the
+// extended plane, of which the two lanes at either end only serve their neighbours (strips overlap by 16 columns and
+// yield 240 columns of outputs each).  A lane whose four columns lie outside the plane holds what the rule puts
+// there — periodic: the group W columns away; mirror: the four columns the rule points to, loaded as one group and
+// reversed; repeated edge: the edge column four times — so every lane finds its neighbours' columns by the same two
+// lane shifts, at the plane's edges too.  (Only the lanes next to the plane feed a stored output.)
+constexpr int kStripCols = 240, kStripHalo = 8;
+
+template <int OP, int K, int S, int PW, int TH>
+__global__ __launch_bounds__(kWave) void pool2d_padded_rows_wide_kernel(const float *__restrict__ x, float *__restrict__ y,
+                                                                        int H, int W, int He, int Ho, int Wo, int pt,
+                                                                        int mode, int nstrips, int64_t planes, float scale)
+{
+    using O = Op<OP>;
+    constexpr int NL = PW;
+    constexpr int NRT = (S == 1) ? K - 1 - PW : (K - 2 - PW > 0 ? K - 2 - PW : 0);
+    constexpr int NOUT = (S == 1) ? 4 : 2;
+    constexpr int NR = (TH - 1) * S + K;
+    static_assert(NL <= 4 && NRT <= 4, "windows reach the immediate neighbour lanes only");
+    const int lane = threadIdx.x;
+    const int sl = (int)(blockIdx.x >> 3);                          // (band, strip) of the plane
+    const int64_t plane = (int64_t)blockIdx.y * kXcd + (blockIdx.x & 7);
+    if (plane >= planes) return;
+    const int band = sl / nstrips, strip = sl - band * nstrips;
+    const int ho0 = band * TH;
+    if (ho0 >= Ho) return;
+    const int c = strip * kStripCols - kStripHalo + 4 * lane;       // my four columns (a multiple of 4: wholly in or out)
+    const bool inside = c >= 0 && c < W;
+    // where an outside lane's columns come from, and how the loaded group is rearranged
+    int src = c;
+    bool reversed = false, all_first = false, all_last = false;
+    if (!inside) {
+        if (mode == SWS_PAD_PERIODIC) src = c < 0 ? c + W : c - W;
+        else if (mode == SWS_PAD_MIRROR) { src = c < 0 ? -c - 3 : 2 * W - 5 - c; reversed = true; }
+        else { src = c < 0 ? 0 : W - 4; all_first = c < 0; all_last = c >= W; }
+        src = src < 0 ? 0 : (src > W - 4 ? W - 4 : src);             // (lanes far outside: any valid group)
+    }
+    const float *xp = x + plane * (int64_t)H * W + src;
+    v4f r[NR];
+#pragma unroll
+    for (int j = 0; j < NR; ++j) {                                   // all loads in flight together
+        const int er = ho0 * S + j;                                  // rows past the extended plane feed no stored output
+        const int row = er < He ? pad_src(er, H, pt, mode) : 0;
+        r[j] = *(const v4f_u *)(xp + (int64_t)row * W);
+    }
+    const bool mine = lane >= kStripHalo / 4 && lane < kWave - kStripHalo / 4 && inside;
+    float *yp = y + plane * (int64_t)Ho * Wo + (S == 1 ? c : c / 2);
+#pragma unroll
+    for (int i = 0; i < TH; ++i) {
+        float e[NL + 4 + NRT];
+        v4f v = r[i * S];
+#pragma unroll
+        for (int a = 1; a < K; ++a) {
+            v.x = O::f(v.x, r[i * S + a].x); v.y = O::f(v.y, r[i * S + a].y);
+            v.z = O::f(v.z, r[i * S + a].z); v.w = O::f(v.w, r[i * S + a].w);
+        }
+        // the rearrangement commutes with the sums down the columns: once per output row
+        const v4f u = reversed ? (v4f){v.w, v.z, v.y, v.x}
+                               : (all_first ? (v4f){v.x, v.x, v.x, v.x} : (all_last ? (v4f){v.w, v.w, v.w, v.w} : v));
+        e[NL] = u.x; e[NL + 1] = u.y; e[NL + 2] = u.z; e[NL + 3] = u.w;
+#pragma unroll
+        for (int t = 0; t < NL; ++t) e[NL - 1 - t] = lane_before(e[NL + 3 - t]);
+#pragma unroll
+        for (int t = 0; t < NRT; ++t) e[NL + 4 + t] = lane_after(e[NL + t]);
+        float o[NOUT];
+#pragma unroll
+        for (int cc = 0; cc < NOUT; ++cc) {
+            float acc = e[cc * S];
+#pragma unroll
+            for (int b = 1; b < K; ++b) acc = O::f(acc, e[cc * S + b]);
+            o[cc] = (OP == SWS_OP_ADD) ? acc * scale : acc;
+        }
+        const int ho = ho0 + i;
+        if (mine && ho < Ho) {
+            if constexpr (NOUT == 4) __builtin_nontemporal_store((v4f){o[0], o[1], o[2], o[3]}, (v4f_u *)(yp + (int64_t)ho * Wo));
+            else {
+                __builtin_nontemporal_store(o[0], yp + (int64_t)ho * Wo);
+                __builtin_nontemporal_store(o[1], yp + (int64_t)ho * Wo + 1);
+            }
+        }
+    }
+}
+
+template <int OP, int K, int S, int PW, int TH>
+hipError_t launch_padded_rows_wide(const float *x, float *y, int64_t planes, int H, int W, int He, int Ho, int Wo, int pt,
+                                   int mode, float scale, hipStream_t s, bool *taken)
+{
+    const int nstrips = (W + kStripCols - 1) / kStripCols;
+    const int bands = (Ho + TH - 1) / TH;
+    const int64_t spp = (int64_t)bands * nstrips;                    // wavefronts per plane
+    const int64_t rounds = (planes + kXcd - 1) / kXcd;
+    *taken = rounds <= 65535 && spp * kXcd <= 2147483647LL;
+    if (!*taken) return hipSuccess;
+    hipLaunchKernelGGL((pool2d_padded_rows_wide_kernel<OP, K, S, PW, TH>), dim3((unsigned)(spp * kXcd), (unsigned)rounds),
+                       dim3(kWave), 0, s, x, y, H, W, He, Ho, Wo, pt, mode, nstrips, planes, scale);
+    return hipGetLastError();
+}
+
 // Band heights as for the kernel without boundary rules: two output rows per lane at stride 1, one at stride 2.
 template <int OP>
 hipError_t dispatch_padded_rows(const float *x, float *y, int64_t planes, int H, int W, int He, int Ho, int Wo, int kh,
@@ -285,8 +383,21 @@ hipError_t dispatch_padded_rows(const float *x, float *y, int64_t planes, int H,
                                 bool *taken)
 {
     *taken = false;
-    if (kh != kw || sh != sw || (W & 3) || W < 4 || W > 256 || g_opt.pool2d_variant != 0) return hipSuccess;
+    if (kh != kw || sh != sw || (W & 3) || W < 4 || g_opt.pool2d_variant != 0) return hipSuccess;
     if (mode != SWS_PAD_MIRROR && mode != SWS_PAD_PERIODIC && mode != SWS_PAD_EDGE) return hipSuccess;
+    if (W > 256) {                                   // strips of 256 columns
+        if (kh == 3 && sh == 1 && pl == 1 && pr == 1)
+            return launch_padded_rows_wide<OP, 3, 1, 1, 2>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
+        if (kh == 5 && sh == 1 && pl == 2 && pr == 2)
+            return launch_padded_rows_wide<OP, 5, 1, 2, 2>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
+        if (kh == 7 && sh == 1 && pl == 3 && pr == 3)
+            return launch_padded_rows_wide<OP, 7, 1, 3, 2>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
+        if (kh == 3 && sh == 2 && pl == 1 && Wo == W / 2)
+            return launch_padded_rows_wide<OP, 3, 2, 1, 1>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
+        if (kh == 2 && sh == 2 && pl == 0 && Wo == W / 2)
+            return launch_padded_rows_wide<OP, 2, 2, 0, 1>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
+        return hipSuccess;
+    }
     if (kh == 3 && sh == 1 && pl == 1 && pr == 1)
         return launch_padded_rows<OP, 3, 1, 1, 2>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
     if (kh == 5 && sh == 1 && pl == 2 && pr == 2)
