@@ -648,10 +648,18 @@ def run_only(torch, B, workloads, name, steps, cold=False):
         y = torch.empty(8, 16, 512, 512, device="cuda")
         op = 1 if opn == "max" else 0
         fn = rotating(xw, y)(lambda xx, yy: B.sws_pool2d_padded(op, xx, k, k, 1, 1, (k // 2,) * 4, mode, 1.0 / (k * k), y=yy))
-    elif name.startswith("wide_"):                        # wide_<avg|max>_k<k>_s<s>: x[8,16,512,512], pad k // 2 (k = 3) or 0 (k = 2)
+    elif name.startswith("pool_"):                        # pool_<planes>x<h>x<w>_<avg|max>_k<k>_s<s>_p<p>: any plain 2-D pooling
+        _, shp, opn, kn, sn, pn = name.split("_")
+        pl_, h_, w_ = (int(v) for v in shp.split("x"))
+        k, st, pd = int(kn[1:]), int(sn[1:]), int(pn[1:])
+        xw = torch.empty(1, pl_, h_, w_, device="cuda").uniform_(-1, 1)
+        y = torch.empty(1, pl_, (h_ + 2 * pd - k) // st + 1, (w_ + 2 * pd - k) // st + 1, device="cuda")
+        op = 1 if opn == "max" else 0
+        fn = rotating(xw, y)(lambda xx, yy: B.sws_pool2d(op, xx, k, k, st, st, pd, pd, 1.0 / (k * k), y=yy))
+    elif name.startswith("wide_"):                        # wide_<avg|max>_k<k>_s<s>: x[8,16,512,512], pad k // 2 (0 for k = 2)
         _, opn, kn, sn = name.split("_")
         k, st = int(kn[1:]), int(sn[1:])
-        pd = 1 if k == 3 else 0
+        pd = 0 if k == 2 else k // 2
         xw = torch.empty(8, 16, 512, 512, device="cuda").uniform_(-1, 1)
         ho = (512 + 2 * pd - k) // st + 1
         y = torch.empty(8, 16, ho, ho, device="cuda")

@@ -684,6 +684,10 @@ hipError_t dispatch_rows(const T *x, T *y, int64_t planes, int H, int W, int Ho,
         // 3 x 3 stride 2 29.5 / 28.8 us — the last stays on the band kernel)
         if (kh == 2 && sh == 2 && pw == 0 && Wo == W / 2)
             return launch_rows_wide<OP, 2, 2, 0, 1, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+        if (kh == 5 && sh == 1 && pw == 2 && Wo == W)
+            return launch_rows_wide<OP, 5, 1, 2, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+        if (kh == 7 && sh == 1 && pw == 3 && Wo == W)
+            return launch_rows_wide<OP, 7, 1, 3, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
         return hipSuccess;
     }
     if (kh == 3 && sh == 1 && pw == 1 && Wo == W)
@@ -692,6 +696,14 @@ hipError_t dispatch_rows(const T *x, T *y, int64_t planes, int H, int W, int Ho,
         return launch_rows<OP, 3, 2, 1, 1, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
     if (kh == 2 && sh == 2 && pw == 0 && Wo == W / 2)
         return launch_rows<OP, 2, 2, 0, 1, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+    // 5 x 5 and 7 x 7 at stride 1: a band of two output rows loads six or eight rows, which pays on wide rows only.
+    // Measured cold, this kernel / the band kernel: [2048,112,112] 5 x 5 38.0 / 54.8 us, 7 x 7 43.7 / 69.0 us;
+    // [8192,56,56] 5 x 5 39.9 / 40.6 us; [32768,28,28] 5 x 5 57.9 / 40.4 us.
+    const bool wide_enough = W >= 64;
+    if (kh == 5 && sh == 1 && pw == 2 && Wo == W && wide_enough)
+        return launch_rows<OP, 5, 1, 2, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+    if (kh == 7 && sh == 1 && pw == 3 && Wo == W && wide_enough)
+        return launch_rows<OP, 7, 1, 3, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
     return hipSuccess;
 }
 
