@@ -624,6 +624,17 @@ def run_only(torch, B, workloads, name, steps, cold=False):
         gy = torch.empty(32, 64, ho, ho, device="cuda").normal_()
         gx = torch.empty(32, 64, 112, 112, device="cuda")
         fn = lambda: B.sws_avgpool2d_grad(gy, 112, 112, 3, 3, s, s, 1, 1, 0, 1 / 9, gx=gx)
+    elif name.startswith("widegrad_"):                    # widegrad_<max|avg>_s<s>: adjoints of 3 x 3 pad 1 pooling on x[8,16,512,512]
+        _, opn, sn = name.split("_")
+        st = int(sn[1:])
+        ho = 512 if st == 1 else 256
+        xw = torch.empty(8, 16, 512, 512, device="cuda").uniform_(-1, 1)
+        gyw = torch.empty(8, 16, ho, ho, device="cuda").normal_()
+        gxw = torch.empty_like(xw)
+        if opn == "max":
+            fn = lambda: B.sws_maxpool2d_grad(xw, gyw, 3, 3, st, st, 1, 1, gx=gxw)
+        else:
+            fn = lambda: B.sws_avgpool2d_grad(gyw, 512, 512, 3, 3, st, st, 1, 1, 0, 1 / 9, gx=gxw)
     elif name in ("grad_cfg3_maxpool_s1", "grad_cfg3_maxpool_s2"):
         x3 = g(workloads.make(3)[0])
         s = int(name[-1])

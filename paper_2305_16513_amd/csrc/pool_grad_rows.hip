@@ -1,6 +1,7 @@
 // Adjoints of 3 x 3 pooling (one column of padding, stride 1 or 2) on planes whose rows fit a
 // wavefront — the backward passes of the row-streaming pooling kernel (Section 2.3 used for
-// training), without LDS.  W a multiple of 4, 4 <= W <= 256; stride 1: Wo = W, stride 2: Wo = W / 2.
+// training), without LDS.  W a multiple of 4 (beyond 256 columns: strips, see locate()); stride 1: Wo = W,
+// stride 2: Wo = W / 2.
 //
 // As in the forward kernel a lane owns four adjacent columns, the W/4 lanes of a group move a row as
 // one contiguous run of 128-bit accesses, the G = 64 / (W/4) groups of a wavefront take G consecutive
@@ -39,24 +40,43 @@ __device__ __forceinline__ int lane_before(int v) { return __builtin_amdgcn_upda
 __device__ __forceinline__ int lane_after(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x130, 0xf, 0xf, false); }
 
 // Where a wavefront's lane works: group (band) and lane within the row; false = nothing to do.
+// Planes wider than 256 columns (nstrips > 0): the wavefront takes one band and a strip of 256 columns of it, of
+// which the two lanes at either end only serve their neighbours — strips overlap by 16 columns and write 240.  A
+// lane whose columns lie outside the plane holds -inf cells and zero gradients, so there are no edge lanes.
+constexpr int kStripCols = 240, kStripHalo = 8;
 struct Where {
-    int l;                  // lane within its row: columns 4l .. 4l + 3
+    int c;                  // my columns: c .. c + 3 (a multiple of 4)
     int r0;                 // first gx row of the band
     int64_t plane;
-    bool first, last;       // the row's edge lanes
+    bool first, last;       // the row's edge lanes (narrow planes)
+    bool inside;            // my columns lie in the plane
+    bool store;             // ... and are mine to write
 };
-__device__ __forceinline__ bool locate(Where &w, int LPR, int G, int lpr_rcp, int TH, int H, int64_t planes)
+__device__ __forceinline__ bool locate(Where &w, int LPR, int G, int lpr_rcp, int TH, int H, int W, int nstrips,
+                                       int64_t planes)
 {
     const int lane = threadIdx.x;
-    const int grp = (lane * lpr_rcp) >> 16;                          // lane / LPR (exact for lane < 64)
-    w.l = lane - grp * LPR;
-    if (grp >= G) return false;
     w.plane = (int64_t)blockIdx.y * kXcd + (blockIdx.x & 7);        // gridDim.x is a multiple of 8: XCD = x & 7
     if (w.plane >= planes) return false;
+    if (nstrips > 0) {
+        const int sl = (int)(blockIdx.x >> 3), band = sl / nstrips, strip = sl - band * nstrips;
+        w.r0 = band * TH;
+        if (w.r0 >= H) return false;
+        w.c = strip * kStripCols - kStripHalo + 4 * lane;
+        w.inside = w.c >= 0 && w.c < W;
+        w.store = w.inside && lane >= kStripHalo / 4 && lane < kWave - kStripHalo / 4;
+        w.first = w.last = false;
+        return true;
+    }
+    const int grp = (lane * lpr_rcp) >> 16;                          // lane / LPR (exact for lane < 64)
+    const int l = lane - grp * LPR;
+    if (grp >= G) return false;
     w.r0 = ((int)(blockIdx.x >> 3) * G + grp) * TH;
     if (w.r0 >= H) return false;
-    w.first = w.l == 0;
-    w.last = w.l == LPR - 1;
+    w.c = 4 * l;
+    w.inside = w.store = true;
+    w.first = l == 0;
+    w.last = l == LPR - 1;
     return true;
 }
 
@@ -97,7 +117,8 @@ __device__ __forceinline__ void row_maxima(const float (&e)[6], int base, float 
 template <int S, int TH>
 __global__ __launch_bounds__(kWave) void maxpool_grad_rows_kernel(const float *__restrict__ x, const float *__restrict__ gy,
                                                                   float *__restrict__ gx, int H, int W, int Ho, int Wo,
-                                                                  int ph, int LPR, int G, int lpr_rcp, int64_t planes)
+                                                                  int ph, int LPR, int G, int lpr_rcp, int nstrips,
+                                                                  int64_t planes)
 {
     static_assert(S == 1 || (S == 2 && TH % 2 == 0), "bands of an even number of rows at stride 2");
     constexpr int NW = S == 1 ? 4 : 2;                               // window columns of a lane
@@ -105,29 +126,30 @@ __global__ __launch_bounds__(kWave) void maxpool_grad_rows_kernel(const float *_
     constexpr int NXR = S == 1 ? TH + 4 : TH + 3;                    // x rows of a band
     const float ninf = -__builtin_huge_valf();
     Where w;
-    if (!locate(w, LPR, G, lpr_rcp, TH, H, planes)) return;
+    if (!locate(w, LPR, G, lpr_rcp, TH, H, W, nstrips, planes)) return;
     const int hf = S == 1 ? w.r0 + ph - 2 : (w.r0 + ph - 1) >> 1;    // first window row (may be < 0)
     const int xr0 = S == 1 ? w.r0 - 2 : 2 * hf - ph;                 // first x row (may be < 0)
     const int d0 = S == 1 ? 2 : w.r0 - xr0;                          // cell row t is x row j = d0 + t
-    const float *xp = x + w.plane * (int64_t)H * W + 4 * w.l;
-    const float *gp = gy + w.plane * (int64_t)Ho * Wo + NW * w.l;
-    float *op = gx + w.plane * (int64_t)H * W + 4 * w.l;
+    const int cc = w.inside ? w.c : 0;                               // (lanes outside the plane read column 0 and drop it)
+    const float *xp = x + w.plane * (int64_t)H * W + cc;
+    const float *gp = gy + w.plane * (int64_t)Ho * Wo + (NW == 4 ? cc : cc / 2);
+    float *op = gx + w.plane * (int64_t)H * W + cc;
 
-    // ---- all loads in flight together; rows outside the plane: -inf cells, zero gradients
+    // ---- all loads in flight together; rows and columns outside the plane: -inf cells, zero gradients
     v4f xr[NXR];
 #pragma unroll
     for (int j = 0; j < NXR; ++j) {
         const int row = xr0 + j;
-        const bool ok = row >= 0 && row < H;
-        const v4f v = *(const v4f_u *)(xp + (int64_t)(ok ? row : 0) * W);
+        const bool in_rows = row >= 0 && row < H, ok = in_rows && w.inside;
+        const v4f v = *(const v4f_u *)(xp + (int64_t)(in_rows ? row : 0) * W);
         xr[j] = ok ? v : (v4f){ninf, ninf, ninf, ninf};
     }
     float g[NWR][NW];
 #pragma unroll
     for (int i = 0; i < NWR; ++i) {
         const int ho = hf + i;
-        const bool ok = ho >= 0 && ho < Ho;
-        const float *src = gp + (int64_t)(ok ? ho : 0) * Wo;
+        const bool in_rows = ho >= 0 && ho < Ho, ok = in_rows && w.inside;
+        const float *src = gp + (int64_t)(in_rows ? ho : 0) * Wo;
         if constexpr (NW == 4) {
             const v4f v = *(const v4f_u *)src;
             g[i][0] = ok ? v.x : 0.0f; g[i][1] = ok ? v.y : 0.0f; g[i][2] = ok ? v.z : 0.0f; g[i][3] = ok ? v.w : 0.0f;
@@ -222,7 +244,7 @@ __global__ __launch_bounds__(kWave) void maxpool_grad_rows_kernel(const float *_
             }
             o[v] = acc;
         }
-        if (row < H) __builtin_nontemporal_store((v4f){o[0], o[1], o[2], o[3]}, (v4f_u *)(op + (int64_t)row * W));
+        if (row < H && w.store) __builtin_nontemporal_store((v4f){o[0], o[1], o[2], o[3]}, (v4f_u *)(op + (int64_t)row * W));
     }
 }
 
@@ -232,23 +254,24 @@ __global__ __launch_bounds__(kWave) void maxpool_grad_rows_kernel(const float *_
 template <int TH>
 __global__ __launch_bounds__(kWave) void avgpool_grad_rows_s2_kernel(const float *__restrict__ gy, float *__restrict__ gx,
                                                                      int H, int W, int Ho, int Wo, int ph, int LPR, int G,
-                                                                     int lpr_rcp, int64_t planes, float scale)
+                                                                     int lpr_rcp, int nstrips, int64_t planes, float scale)
 {
     static_assert(TH % 2 == 0, "bands of an even number of rows");
     constexpr int NWR = TH / 2 + 1;
     Where w;
-    if (!locate(w, LPR, G, lpr_rcp, TH, H, planes)) return;
+    if (!locate(w, LPR, G, lpr_rcp, TH, H, W, nstrips, planes)) return;
     const int hf = (w.r0 + ph - 1) >> 1;
     const int d0 = w.r0 - (2 * hf - ph);                             // 1 or 2
-    const float *gp = gy + w.plane * (int64_t)Ho * Wo + 2 * w.l;
-    float *op = gx + w.plane * (int64_t)H * W + 4 * w.l;
+    const int cc = w.inside ? w.c : 0;
+    const float *gp = gy + w.plane * (int64_t)Ho * Wo + cc / 2;
+    float *op = gx + w.plane * (int64_t)H * W + cc;
     // per window row: the sums along W that the lane's four cells receive
     float c[NWR][4];
 #pragma unroll
     for (int i = 0; i < NWR; ++i) {
         const int ho = hf + i;
-        const bool ok = ho >= 0 && ho < Ho;
-        const v2f v = *(const v2f_u *)(gp + (int64_t)(ok ? ho : 0) * Wo);
+        const bool in_rows = ho >= 0 && ho < Ho, ok = in_rows && w.inside;
+        const v2f v = *(const v2f_u *)(gp + (int64_t)(in_rows ? ho : 0) * Wo);
         const float g0 = ok ? v.x * scale : 0.0f, g1 = ok ? v.y * scale : 0.0f;
         const float t = lane_after(g0);
         const float ga = w.last ? 0.0f : t;
@@ -266,25 +289,33 @@ __global__ __launch_bounds__(kWave) void avgpool_grad_rows_s2_kernel(const float
             for (int i = 0; i < NWR; ++i) acc += (2 * i <= j && j <= 2 * i + 2) ? c[i][v] : 0.0f;
             o[v] = acc;
         }
-        if (row < H) __builtin_nontemporal_store((v4f){o[0], o[1], o[2], o[3]}, (v4f_u *)(op + (int64_t)row * W));
+        if (row < H && w.store) __builtin_nontemporal_store((v4f){o[0], o[1], o[2], o[3]}, (v4f_u *)(op + (int64_t)row * W));
     }
 }
 
 struct RowsGrid {
-    int LPR, G, rcp;
+    int LPR, G, rcp, nstrips;
     dim3 grid;
     bool ok;
 };
 RowsGrid rows_grid(int64_t planes, int H, int W, int TH)
 {
     RowsGrid r;
-    r.LPR = W / 4;
-    r.G = kWave / r.LPR;
-    r.rcp = (65536 + r.LPR - 1) / r.LPR;
     const int bands = (H + TH - 1) / TH;
-    const int spp = (bands + r.G - 1) / r.G;                         // wavefronts per plane
     const int64_t rounds = (planes + kXcd - 1) / kXcd;
-    r.ok = rounds <= 65535;
+    int64_t spp;                                                     // wavefronts per plane
+    if (W > 256) {                                                   // strips of 256 columns
+        r.LPR = kWave; r.G = 1; r.rcp = 0;
+        r.nstrips = (W + kStripCols - 1) / kStripCols;
+        spp = (int64_t)bands * r.nstrips;
+    } else {
+        r.LPR = W / 4;
+        r.G = kWave / r.LPR;
+        r.rcp = (65536 + r.LPR - 1) / r.LPR;
+        r.nstrips = 0;
+        spp = (bands + r.G - 1) / r.G;
+    }
+    r.ok = rounds <= 65535 && spp * kXcd <= 2147483647LL;
     r.grid = dim3((unsigned)(spp * kXcd), (unsigned)rounds);
     return r;
 }
@@ -292,7 +323,7 @@ RowsGrid rows_grid(int64_t planes, int H, int W, int TH)
 bool rows_shape(int H, int W, int Ho, int Wo, int kh, int kw, int sh, int sw, int ph, int pw)
 {
     if (kh != 3 || kw != 3 || sh != sw || (sh != 1 && sh != 2) || pw != 1 || ph < 0 || ph > 2) return false;
-    if ((W & 3) || W < 4 || W > 256 || H < 1) return false;
+    if ((W & 3) || W < 4 || H < 1) return false;
     return sh == 1 ? Wo == W : Wo == W / 2;
 }
 
@@ -309,10 +340,10 @@ hipError_t launch_maxpool2d_grad_rows(const float *x, const float *gy, float *gx
     *taken = true;
     if (sh == 1)
         hipLaunchKernelGGL((maxpool_grad_rows_kernel<1, TH1>), r.grid, dim3(kWave), 0, s, x, gy, gx, H, W, Ho, Wo, ph, r.LPR,
-                           r.G, r.rcp, planes);
+                           r.G, r.rcp, r.nstrips, planes);
     else
         hipLaunchKernelGGL((maxpool_grad_rows_kernel<2, TH2>), r.grid, dim3(kWave), 0, s, x, gy, gx, H, W, Ho, Wo, ph, r.LPR,
-                           r.G, r.rcp, planes);
+                           r.G, r.rcp, r.nstrips, planes);
     return hipGetLastError();
 }
 
@@ -326,7 +357,7 @@ hipError_t launch_avgpool2d_grad_rows(const float *gy, float *gx, int64_t planes
     if (!r.ok) return hipSuccess;
     *taken = true;
     hipLaunchKernelGGL((avgpool_grad_rows_s2_kernel<TH>), r.grid, dim3(kWave), 0, s, gy, gx, H, W, Ho, Wo, ph, r.LPR, r.G,
-                       r.rcp, planes, scale);
+                       r.rcp, r.nstrips, planes, scale);
     return hipGetLastError();
 }
 

@@ -157,7 +157,9 @@ def test_avgpool2d_grad_argument_checks(B):
 
 # ------------------------------------------------------------------ the row-streaming adjoints (3 x 3, rows of 4 .. 256)
 ROW_PLANES = [(1, 1, 1, 4), (1, 3, 2, 8), (2, 5, 7, 12), (1, 9, 9, 60), (3, 3, 37, 112), (1, 2, 113, 256), (1, 17, 6, 20),
-              (2, 2, 56, 56), (1, 1, 300, 16)]
+              (2, 2, 56, 56), (1, 1, 300, 16),
+              # wider than a wavefront's 256 columns: strips (planes that end inside a strip, on a strip boundary, past one)
+              (1, 3, 21, 260), (1, 2, 9, 480), (1, 1, 14, 484), (1, 9, 6, 512), (1, 1, 5, 1000)]
 
 
 @pytest.mark.parametrize("variant", [0, 128])
@@ -216,13 +218,14 @@ def test_row_streaming_adjoints_guard_band(B):
     import torch
     r = np.random.Generator(np.random.PCG64(77))
     for stride in (1, 2):
-        x = torch.from_numpy(r.standard_normal((3, 3, 21, 36), dtype=np.float32)).cuda()
-        ho, wo = (21 + 2 - 3) // stride + 1, (36 + 2 - 3) // stride + 1
+      for wdt in (36, 500):
+        x = torch.from_numpy(r.standard_normal((3, 3, 21, wdt), dtype=np.float32)).cuda()
+        ho, wo = (21 + 2 - 3) // stride + 1, (wdt + 2 - 3) // stride + 1
         gy = torch.from_numpy(r.standard_normal((3, 3, ho, wo), dtype=np.float32)).cuda()
         n = x.numel()
         for fn in (lambda out: B.sws_maxpool2d_grad(x, gy, 3, 3, stride, stride, 1, 1, gx=out),
-                   lambda out: B.sws_avgpool2d_grad(gy, 21, 36, 3, 3, stride, stride, 1, 1, scale=1 / 9, gx=out)):
+                   lambda out: B.sws_avgpool2d_grad(gy, 21, wdt, 3, 3, stride, stride, 1, 1, scale=1 / 9, gx=out)):
             buf = torch.full((n + 256,), 7.0, device="cuda")
-            fn(buf[128:128 + n].view(3, 3, 21, 36))
+            fn(buf[128:128 + n].view(3, 3, 21, wdt))
             torch.cuda.synchronize()
             assert bool((buf[:128] == 7.0).all()) and bool((buf[128 + n:] == 7.0).all())
