@@ -219,14 +219,25 @@ __global__ __launch_bounds__(kWave) void pool2d_padded_rows_kernel(const float *
         r[j] = *(const v4f_u *)(xp + (int64_t)row * W);
     }
     const bool first = l == 0, last = l == LPR - 1;
+    // the sums down the columns of all TH output rows at once where they share rows (stride 1)
+    v4f vs[TH];
+    if constexpr (S == 1) {
+        windows_shared<K, TH>(r, vs, [](v4f a, v4f b) {
+            return (v4f){O::f(a.x, b.x), O::f(a.y, b.y), O::f(a.z, b.z), O::f(a.w, b.w)};
+        });
+    }
 #pragma unroll
     for (int i = 0; i < TH; ++i) {
         float e[NL + 4 + NRT];
         v4f v = r[i * S];
+        if constexpr (S == 1) {
+            v = vs[i];
+        } else {
 #pragma unroll
-        for (int a = 1; a < K; ++a) {
-            v.x = O::f(v.x, r[i * S + a].x); v.y = O::f(v.y, r[i * S + a].y);
-            v.z = O::f(v.z, r[i * S + a].z); v.w = O::f(v.w, r[i * S + a].w);
+            for (int a = 1; a < K; ++a) {
+                v.x = O::f(v.x, r[i * S + a].x); v.y = O::f(v.y, r[i * S + a].y);
+                v.z = O::f(v.z, r[i * S + a].z); v.w = O::f(v.w, r[i * S + a].w);
+            }
         }
         e[NL] = v.x; e[NL + 1] = v.y; e[NL + 2] = v.z; e[NL + 3] = v.w;
         const float own[4] = {v.x, v.y, v.z, v.w};
@@ -245,12 +256,18 @@ __global__ __launch_bounds__(kWave) void pool2d_padded_rows_kernel(const float *
             e[NL + 4 + t] = last ? edge : nb;
         }
         float o[NOUT];
+        if constexpr (S == 1) {
+            windows_shared<K, NOUT>(e, o, [](float a, float b) { return O::f(a, b); });
 #pragma unroll
-        for (int c = 0; c < NOUT; ++c) {
-            float acc = e[c * S];
+            for (int cc = 0; cc < NOUT; ++cc) o[cc] = (OP == SWS_OP_ADD) ? o[cc] * scale : o[cc];
+        } else {
 #pragma unroll
-            for (int b = 1; b < K; ++b) acc = O::f(acc, e[c * S + b]);
-            o[c] = (OP == SWS_OP_ADD) ? acc * scale : acc;
+            for (int cc = 0; cc < NOUT; ++cc) {
+                float acc = e[cc * S];
+#pragma unroll
+                for (int b = 1; b < K; ++b) acc = O::f(acc, e[cc * S + b]);
+                o[cc] = (OP == SWS_OP_ADD) ? acc * scale : acc;
+            }
         }
         const int ho = ho0 + i;
         if (ho < Ho) {
@@ -296,7 +313,7 @@ __global__ __launch_bounds__(kWave) void pool2d_padded_rows_wide_kernel(const fl
     constexpr int NRT = (S == 1) ? K - 1 - PW : (K - 2 - PW > 0 ? K - 2 - PW : 0);
     constexpr int NOUT = (S == 1) ? 4 : 2;
     constexpr int NR = (TH - 1) * S + K;
-    static_assert(NL <= 4 && NRT <= 4, "windows reach the immediate neighbour lanes only");
+    static_assert(NL <= kStripHalo && NRT <= kStripHalo, "windows reach no further than the lanes a strip gives away");
     const int lane = threadIdx.x;
     const int sl = (int)(blockIdx.x >> 3);                          // (band, strip) of the plane
     const int64_t plane = (int64_t)blockIdx.y * kXcd + (blockIdx.x & 7);
@@ -325,30 +342,54 @@ __global__ __launch_bounds__(kWave) void pool2d_padded_rows_wide_kernel(const fl
     }
     const bool mine = lane >= kStripHalo / 4 && lane < kWave - kStripHalo / 4 && inside;
     float *yp = y + plane * (int64_t)Ho * Wo + (S == 1 ? c : c / 2);
+    // the sums down the columns of all TH output rows at once where they share rows (stride 1)
+    v4f vs[TH];
+    if constexpr (S == 1) {
+        windows_shared<K, TH>(r, vs, [](v4f a, v4f b) {
+            return (v4f){O::f(a.x, b.x), O::f(a.y, b.y), O::f(a.z, b.z), O::f(a.w, b.w)};
+        });
+    }
 #pragma unroll
     for (int i = 0; i < TH; ++i) {
         float e[NL + 4 + NRT];
         v4f v = r[i * S];
+        if constexpr (S == 1) {
+            v = vs[i];
+        } else {
 #pragma unroll
-        for (int a = 1; a < K; ++a) {
-            v.x = O::f(v.x, r[i * S + a].x); v.y = O::f(v.y, r[i * S + a].y);
-            v.z = O::f(v.z, r[i * S + a].z); v.w = O::f(v.w, r[i * S + a].w);
+            for (int a = 1; a < K; ++a) {
+                v.x = O::f(v.x, r[i * S + a].x); v.y = O::f(v.y, r[i * S + a].y);
+                v.z = O::f(v.z, r[i * S + a].z); v.w = O::f(v.w, r[i * S + a].w);
+            }
         }
         // the rearrangement commutes with the sums down the columns: once per output row
         const v4f u = reversed ? (v4f){v.w, v.z, v.y, v.x}
                                : (all_first ? (v4f){v.x, v.x, v.x, v.x} : (all_last ? (v4f){v.w, v.w, v.w, v.w} : v));
         e[NL] = u.x; e[NL + 1] = u.y; e[NL + 2] = u.z; e[NL + 3] = u.w;
+        // column -(t + 1) of my four is element 3 - t % 4 of the lane t / 4 + 1 before me: one or two lane shifts
 #pragma unroll
-        for (int t = 0; t < NL; ++t) e[NL - 1 - t] = lane_before(e[NL + 3 - t]);
+        for (int t = 0; t < NL; ++t) {
+            const float one = lane_before(e[NL + 3 - (t & 3)]);
+            e[NL - 1 - t] = t < 4 ? one : lane_before(one);
+        }
 #pragma unroll
-        for (int t = 0; t < NRT; ++t) e[NL + 4 + t] = lane_after(e[NL + t]);
+        for (int t = 0; t < NRT; ++t) {
+            const float one = lane_after(e[NL + (t & 3)]);
+            e[NL + 4 + t] = t < 4 ? one : lane_after(one);
+        }
         float o[NOUT];
+        if constexpr (S == 1) {
+            windows_shared<K, NOUT>(e, o, [](float a, float b) { return O::f(a, b); });
 #pragma unroll
-        for (int cc = 0; cc < NOUT; ++cc) {
-            float acc = e[cc * S];
+            for (int cc = 0; cc < NOUT; ++cc) o[cc] = (OP == SWS_OP_ADD) ? o[cc] * scale : o[cc];
+        } else {
 #pragma unroll
-            for (int b = 1; b < K; ++b) acc = O::f(acc, e[cc * S + b]);
-            o[cc] = (OP == SWS_OP_ADD) ? acc * scale : acc;
+            for (int cc = 0; cc < NOUT; ++cc) {
+                float acc = e[cc * S];
+#pragma unroll
+                for (int b = 1; b < K; ++b) acc = O::f(acc, e[cc * S + b]);
+                o[cc] = (OP == SWS_OP_ADD) ? acc * scale : acc;
+            }
         }
         const int ho = ho0 + i;
         if (mine && ho < Ho) {
@@ -391,19 +432,31 @@ hipError_t dispatch_padded_rows(const float *x, float *y, int64_t planes, int H,
         if (kh == 5 && sh == 1 && pl == 2 && pr == 2)
             return launch_padded_rows_wide<OP, 5, 1, 2, 2>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
         if (kh == 7 && sh == 1 && pl == 3 && pr == 3)
-            return launch_padded_rows_wide<OP, 7, 1, 3, 2>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
+            return launch_padded_rows_wide<OP, 7, 1, 3, 4>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
+        if (kh == 9 && sh == 1 && pl == 4 && pr == 4)
+            return launch_padded_rows_wide<OP, 9, 1, 4, 4>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
+        if (kh == 11 && sh == 1 && pl == 5 && pr == 5)
+            return launch_padded_rows_wide<OP, 11, 1, 5, 4>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
+        if (kh == 13 && sh == 1 && pl == 6 && pr == 6)
+            return launch_padded_rows_wide<OP, 13, 1, 6, 4>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
         if (kh == 3 && sh == 2 && pl == 1 && Wo == W / 2)
             return launch_padded_rows_wide<OP, 3, 2, 1, 1>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
         if (kh == 2 && sh == 2 && pl == 0 && Wo == W / 2)
             return launch_padded_rows_wide<OP, 2, 2, 0, 1>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
         return hipSuccess;
     }
+    if (kh == 9 && sh == 1 && pl == 4 && pr == 4 && W >= 64)   // (four and more virtual columns a side: the strip kernel, one strip)
+        return launch_padded_rows_wide<OP, 9, 1, 4, 4>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
+    if (kh == 11 && sh == 1 && pl == 5 && pr == 5 && W >= 64)
+        return launch_padded_rows_wide<OP, 11, 1, 5, 4>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
+    if (kh == 13 && sh == 1 && pl == 6 && pr == 6 && W >= 64)
+        return launch_padded_rows_wide<OP, 13, 1, 6, 4>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
     if (kh == 3 && sh == 1 && pl == 1 && pr == 1)
         return launch_padded_rows<OP, 3, 1, 1, 2>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
     if (kh == 5 && sh == 1 && pl == 2 && pr == 2)
         return launch_padded_rows<OP, 5, 1, 2, 2>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
     if (kh == 7 && sh == 1 && pl == 3 && pr == 3)
-        return launch_padded_rows<OP, 7, 1, 3, 2>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
+        return launch_padded_rows<OP, 7, 1, 3, 4>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
     if (kh == 3 && sh == 2 && pl == 1 && Wo == W / 2)
         return launch_padded_rows<OP, 3, 2, 1, 1>(x, y, planes, H, W, He, Ho, Wo, pt, mode, scale, s, taken);
     if (kh == 2 && sh == 2 && pl == 0 && Wo == W / 2)

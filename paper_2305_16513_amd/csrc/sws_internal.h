@@ -55,6 +55,43 @@ template <> struct Op<SWS_OP_MIN> {
     static __device__ __forceinline__ float f(float a, float b) { return __builtin_fminf(a, b); }
 };
 
+// N sliding windows of K consecutive elements at stride 1, out[j] = in[j] (+) ... (+) in[j + K - 1], from what they
+// share: the elements N - 1 .. K - 1 lie in all of them and are combined once; window j puts the rest of the head
+// in front (in[j] .. in[N - 2]) and the start of the tail behind (in[K] .. in[K + j - 1]) — Section 3's suffix /
+// prefix split between registers.  K + 3N - 6 operations instead of N (K - 1); operand order is kept.
+// F(a, b) combines two elements (floats, or vectors of columns).
+template <int K, int N, typename E, typename F>
+__device__ __forceinline__ void windows_shared(const E *in, E *out, F f)
+{
+    // (windows of fewer than five elements are combined left to right as Eq. 3 writes them: nothing to gain, and the
+    // strided kernels, which share nothing, then give the same bits)
+    if constexpr (N < 2 || K < N || K < 5 || K + 3 * N - 6 >= N * (K - 1)) {
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            E acc = in[j];
+#pragma unroll
+            for (int b = 1; b < K; ++b) acc = f(acc, in[j + b]);
+            out[j] = acc;
+        }
+    } else {
+        E core = in[N - 1];
+#pragma unroll
+        for (int b = N; b < K; ++b) core = f(core, in[b]);
+        E head[N - 1], tail[N - 1];                  // head[j] = in[j] .. in[N-2];  tail[j] = in[K] .. in[K+j]
+        head[N - 2] = in[N - 2];
+#pragma unroll
+        for (int j = N - 3; j >= 0; --j) head[j] = f(in[j], head[j + 1]);
+        tail[0] = in[K];
+#pragma unroll
+        for (int j = 1; j < N - 1; ++j) tail[j] = f(tail[j - 1], in[K + j]);
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            E acc = j < N - 1 ? f(head[j], core) : core;
+            out[j] = j > 0 ? f(acc, tail[j - 1]) : acc;
+        }
+    }
+}
+
 // Boundary conditions of a row extended by pad_left virtual elements in front (and more behind):
 // the physical index that virtual element e stands for, or -1 for the operator's identity.
 // mode: SWS_PAD_IDENTITY, SWS_PAD_MIRROR (x[-i] = x[i]), SWS_PAD_PERIODIC (x[-i] = x[len-i]),

@@ -83,7 +83,7 @@ ROW_SHAPES = [(1, 1, 1, 4), (2, 3, 5, 8), (3, 2, 9, 28), (2, 9, 56, 56), (1, 11,
 
 @pytest.mark.parametrize("band_kernel", [False, True])
 @pytest.mark.parametrize("op", ["add", "max", "min"])
-@pytest.mark.parametrize("geom", [(3, 1, 1), (3, 2, 1), (2, 2, 0), (5, 1, 2), (7, 1, 3)])
+@pytest.mark.parametrize("geom", [(3, 1, 1), (3, 2, 1), (2, 2, 0), (5, 1, 2), (7, 1, 3), (9, 1, 4), (11, 1, 5), (13, 1, 6)])
 @pytest.mark.parametrize("shape", ROW_SHAPES)
 def test_row_streaming_kernel(B, band_kernel, op, geom, shape):
     """3 x 3 pad 1 at stride 1 and 2 and 2 x 2 stride 2 on rows of 4 .. 256 elements (multiples of 4) run on the
@@ -309,7 +309,7 @@ def test_small_planes_four_sided_padding_and_real_cell_average(B, divisor, geom,
 
 
 @pytest.mark.parametrize("op", ["add", "max", "min"])
-@pytest.mark.parametrize("geom", [(3, 1, 1), (3, 2, 1), (2, 2, 0), (5, 1, 2), (7, 1, 3)])
+@pytest.mark.parametrize("geom", [(3, 1, 1), (3, 2, 1), (2, 2, 0), (5, 1, 2), (7, 1, 3), (9, 1, 4), (11, 1, 5), (13, 1, 6)])
 @pytest.mark.parametrize("shape", [(2, 3, 37, 260), (1, 2, 20, 512), (1, 1, 9, 1000), (9, 1, 6, 480), (1, 2, 11, 244 + 240)])
 def test_row_streaming_kernel_on_strips_of_wide_planes(B, op, geom, shape):
     """The same windows on planes wider than 256 columns: strips of 256 input columns whose end lanes only serve

@@ -81,7 +81,8 @@ def test_planes_wider_than_a_slice_are_cut_into_column_tiles(B, mode, op, geom, 
 @pytest.mark.parametrize("mode", ["mirror", "periodic", "edge"])
 @pytest.mark.parametrize("W", [4, 8, 28, 60, 112, 200, 256, 260, 480, 484, 512, 1000])
 def test_row_streaming_kernel_shapes(B, mode, W):
-    """3 x 3 (one virtual column a side), 5 x 5 (two), 7 x 7 (three) and 2 x 2 stride 2 on rows of 4 .. 256 elements:
+    """3 x 3 (one virtual column a side), 5 x 5 (two), 7 x 7 (three), 9 x 9 to 13 x 13 (four to six: the strip form on
+    rows of 64 and more) and 2 x 2 stride 2 on rows of 4 .. 256 elements:
     several groups per wavefront, bands that end inside a group, unequal virtual rows above and below.  Wider rows:
     strips of 256 columns whose outside lanes hold what the rule puts there (planes that end inside a strip, exactly
     on a strip boundary, four columns past one)."""
@@ -91,7 +92,11 @@ def test_row_streaming_kernel_shapes(B, mode, W):
         xi = r.integers(-9, 10, size=(1, 9, H, W)).astype(np.float32)
         for kh, s, pads in ((3, 1, (1, 1, 1, 1)), (3, 1, (4, 1, 0, 1)), (3, 2, (1, 1, 1, 1)), (3, 2, (0, 1, 3, 0)),
                             (2, 2, (0, 0, 0, 0)), (2, 2, (1, 0, 2, 1)), (2, 2, (3, 0, 0, 0)),
-                            (5, 1, (2, 2, 2, 2)), (5, 1, (0, 2, 4, 2)), (7, 1, (3, 3, 3, 3)), (7, 1, (4, 3, 2, 3))):
+                            (5, 1, (2, 2, 2, 2)), (5, 1, (0, 2, 4, 2)), (7, 1, (3, 3, 3, 3)), (7, 1, (4, 3, 2, 3)),
+                            (9, 1, (4, 4, 4, 4)), (9, 1, (0, 4, 8, 4)), (11, 1, (5, 5, 5, 5)), (13, 1, (6, 6, 6, 6)),
+                            (13, 1, (9, 6, 3, 6))):
+            if max(pads[0], pads[2]) > H - 1 or max(pads[1], pads[3]) > W - 1:
+                continue                                 # (a mirrored or periodic pad cannot exceed the plane)
             for op in (0, 1, 2):
                 _check(B, op, x, kh, kh, s, s, pads, MODES[mode], what="rows")
             y = to_host(B.sws_pool2d_padded(0, to_gpu(xi), kh, kh, s, s, pads, MODES[mode], 1.0))
