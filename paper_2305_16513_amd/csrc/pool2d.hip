@@ -494,7 +494,7 @@ __device__ __forceinline__ float lane_after(float v)        // the value held by
 template <int OP, int K, int S, int PW, int TH, typename T>
 __global__ __launch_bounds__(kWave) void pool2d_rows_kernel(const T *__restrict__ x, T *__restrict__ y, int H, int W,
                                                             int Ho, int Wo, int ph, int LPR, int G, int lpr_rcp,
-                                                            int64_t planes, float scale)
+                                                            int64_t planes, float scale, int div_valid)
 {
     using O = Op<OP>;
     using IO = Io<T>;
@@ -574,6 +574,16 @@ __global__ __launch_bounds__(kWave) void pool2d_rows_kernel(const T *__restrict_
             }
         }
         const int ho = ho0 + i;
+        if (OP == SWS_OP_ADD && div_valid) {                         // the average over the cells inside the plane
+            const int h0 = ho * S - ph;
+            const int rows_in = (h0 + K < H ? h0 + K : H) - (h0 > 0 ? h0 : 0);
+#pragma unroll
+            for (int cc = 0; cc < NOUT; ++cc) {
+                const int c0 = (NOUT * l + cc) * S - PW;
+                const int cols_in = (c0 + K < W ? c0 + K : W) - (c0 > 0 ? c0 : 0);
+                o[cc] = o[cc] / (float)(rows_in * cols_in);
+            }
+        }
         if (ho < Ho) {
             if constexpr (NOUT == 4) IO::store4(yp + (int64_t)ho * Wo, (v4f){o[0], o[1], o[2], o[3]}, false);
             else IO::store2_nt(yp + (int64_t)ho * Wo, (v2f){o[0], o[1]});
@@ -583,7 +593,7 @@ __global__ __launch_bounds__(kWave) void pool2d_rows_kernel(const T *__restrict_
 
 template <int OP, int K, int S, int PW, int TH, typename T>
 hipError_t launch_rows(const T *x, T *y, int64_t planes, int H, int W, int Ho, int Wo, int ph, float scale,
-                       hipStream_t s, bool *taken)
+                       int div_valid, hipStream_t s, bool *taken)
 {
     const int LPR = W / 4, G = kWave / LPR;
     const int bands = (Ho + TH - 1) / TH;
@@ -592,7 +602,7 @@ hipError_t launch_rows(const T *x, T *y, int64_t planes, int H, int W, int Ho, i
     *taken = rounds <= 65535;
     if (!*taken) return hipSuccess;
     hipLaunchKernelGGL((pool2d_rows_kernel<OP, K, S, PW, TH, T>), dim3((unsigned)(spp * kXcd), (unsigned)rounds), dim3(kWave),
-                       0, s, x, y, H, W, Ho, Wo, ph, LPR, G, (65536 + LPR - 1) / LPR, planes, scale);
+                       0, s, x, y, H, W, Ho, Wo, ph, LPR, G, (65536 + LPR - 1) / LPR, planes, scale, div_valid);
     return hipGetLastError();
 }
 
@@ -606,7 +616,7 @@ constexpr int kStripCols = 240, kStripHalo = 8;
 template <int OP, int K, int S, int PW, int TH, typename T>
 __global__ __launch_bounds__(kWave) void pool2d_rows_wide_kernel(const T *__restrict__ x, T *__restrict__ y, int H, int W,
                                                                  int Ho, int Wo, int ph, int nstrips, int64_t planes,
-                                                                 float scale)
+                                                                 float scale, int div_valid)
 {
     using O = Op<OP>;
     using IO = Io<T>;
@@ -684,6 +694,16 @@ __global__ __launch_bounds__(kWave) void pool2d_rows_wide_kernel(const T *__rest
             }
         }
         const int ho = ho0 + i;
+        if (OP == SWS_OP_ADD && div_valid) {                         // the average over the cells inside the plane
+            const int h0 = ho * S - ph;
+            const int rows_in = (h0 + K < H ? h0 + K : H) - (h0 > 0 ? h0 : 0);
+#pragma unroll
+            for (int cc = 0; cc < NOUT; ++cc) {
+                const int c0 = (S == 1 ? c + cc : c + 2 * cc) - PW;
+                const int cols_in = (c0 + K < W ? c0 + K : W) - (c0 > 0 ? c0 : 0);
+                o[cc] = o[cc] / (float)(rows_in * (cols_in > 0 ? cols_in : 1));
+            }
+        }
         if (mine && ho < Ho) {
             if constexpr (NOUT == 4) IO::store4(yp + (int64_t)ho * Wo, (v4f){o[0], o[1], o[2], o[3]}, false);
             else IO::store2_nt(yp + (int64_t)ho * Wo, (v2f){o[0], o[1]});
@@ -693,7 +713,7 @@ __global__ __launch_bounds__(kWave) void pool2d_rows_wide_kernel(const T *__rest
 
 template <int OP, int K, int S, int PW, int TH, typename T>
 hipError_t launch_rows_wide(const T *x, T *y, int64_t planes, int H, int W, int Ho, int Wo, int ph, float scale,
-                            hipStream_t s, bool *taken)
+                            int div_valid, hipStream_t s, bool *taken)
 {
     const int nstrips = (W + kStripCols - 1) / kStripCols;
     const int bands = (Ho + TH - 1) / TH;
@@ -702,7 +722,7 @@ hipError_t launch_rows_wide(const T *x, T *y, int64_t planes, int H, int W, int 
     *taken = rounds <= 65535 && spp * kXcd <= 2147483647LL;
     if (!*taken) return hipSuccess;
     hipLaunchKernelGGL((pool2d_rows_wide_kernel<OP, K, S, PW, TH, T>), dim3((unsigned)(spp * kXcd), (unsigned)rounds), dim3(kWave),
-                       0, s, x, y, H, W, Ho, Wo, ph, nstrips, planes, scale);
+                       0, s, x, y, H, W, Ho, Wo, ph, nstrips, planes, scale, div_valid);
     return hipGetLastError();
 }
 
@@ -716,48 +736,48 @@ hipError_t dispatch_rows(const T *x, T *y, int64_t planes, int H, int W, int Ho,
                          int sw, int ph, int pw, float scale, int div_valid, hipStream_t s, bool *taken)
 {
     *taken = false;
-    if (div_valid || kh != kw || sh != sw || (W & 3) || W < 4 || ph < 0 || ph >= kh || (g_opt.pool2d_variant & 128))
+    if (kh != kw || sh != sw || (W & 3) || W < 4 || ph < 0 || ph >= kh || (g_opt.pool2d_variant & 128))
         return hipSuccess;
     if (W > 256) {                                   // strips of 256 columns
         if (kh == 3 && sh == 1 && pw == 1 && Wo == W)
-            return launch_rows_wide<OP, 3, 1, 1, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+            return launch_rows_wide<OP, 3, 1, 1, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
         // (measured on [128, 512, 512], cold, strips / band kernel: 3 x 3 stride 1 50 / 95 us, 2 x 2 stride 2 27.8 / 29.2 us,
         // 3 x 3 stride 2 29.5 / 28.8 us — the last stays on the band kernel)
         if (kh == 2 && sh == 2 && pw == 0 && Wo == W / 2)
-            return launch_rows_wide<OP, 2, 2, 0, 1, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+            return launch_rows_wide<OP, 2, 2, 0, 1, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
         if (kh == 5 && sh == 1 && pw == 2 && Wo == W)
-            return launch_rows_wide<OP, 5, 1, 2, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+            return launch_rows_wide<OP, 5, 1, 2, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
         if (kh == 7 && sh == 1 && pw == 3 && Wo == W)
-            return launch_rows_wide<OP, 7, 1, 3, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+            return launch_rows_wide<OP, 7, 1, 3, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
         if (kh == 9 && sh == 1 && pw == 4 && Wo == W)
-            return launch_rows_wide<OP, 9, 1, 4, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+            return launch_rows_wide<OP, 9, 1, 4, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
         if (kh == 11 && sh == 1 && pw == 5 && Wo == W)
-            return launch_rows_wide<OP, 11, 1, 5, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+            return launch_rows_wide<OP, 11, 1, 5, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
         if (kh == 13 && sh == 1 && pw == 6 && Wo == W)
-            return launch_rows_wide<OP, 13, 1, 6, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+            return launch_rows_wide<OP, 13, 1, 6, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
         return hipSuccess;
     }
     if (kh == 3 && sh == 1 && pw == 1 && Wo == W)
-        return launch_rows<OP, 3, 1, 1, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+        return launch_rows<OP, 3, 1, 1, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
     if (kh == 3 && sh == 2 && pw == 1 && Wo == W / 2)
-        return launch_rows<OP, 3, 2, 1, 1, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+        return launch_rows<OP, 3, 2, 1, 1, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
     if (kh == 2 && sh == 2 && pw == 0 && Wo == W / 2)
-        return launch_rows<OP, 2, 2, 0, 1, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+        return launch_rows<OP, 2, 2, 0, 1, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
     // 5 x 5 and 7 x 7 at stride 1: a band of two output rows loads six or eight rows, which pays on wide rows only.
     // Measured cold, this kernel / the band kernel: [2048,112,112] 5 x 5 38.0 / 54.8 us, 7 x 7 43.7 / 69.0 us;
     // [8192,56,56] 5 x 5 39.9 / 40.6 us; [32768,28,28] 5 x 5 57.9 / 40.4 us.
     const bool wide_enough = W >= 64;
     if (kh == 5 && sh == 1 && pw == 2 && Wo == W && wide_enough)
-        return launch_rows<OP, 5, 1, 2, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+        return launch_rows<OP, 5, 1, 2, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
     if (kh == 7 && sh == 1 && pw == 3 && Wo == W && wide_enough)
-        return launch_rows<OP, 7, 1, 3, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+        return launch_rows<OP, 7, 1, 3, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
     if (kh == 9 && sh == 1 && pw == 4 && Wo == W && wide_enough)
-        return launch_rows<OP, 9, 1, 4, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+        return launch_rows<OP, 9, 1, 4, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
     // windows that reach two lanes away: the strip form (one strip), whose outside lanes stand in for the edges
     if (kh == 11 && sh == 1 && pw == 5 && Wo == W && wide_enough)
-        return launch_rows_wide<OP, 11, 1, 5, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+        return launch_rows_wide<OP, 11, 1, 5, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
     if (kh == 13 && sh == 1 && pw == 6 && Wo == W && wide_enough)
-        return launch_rows_wide<OP, 13, 1, 6, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, s, taken);
+        return launch_rows_wide<OP, 13, 1, 6, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
     return hipSuccess;
 }
 

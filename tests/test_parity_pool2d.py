@@ -346,3 +346,29 @@ def test_row_streaming_kernel_on_strips_of_wide_planes(B, op, geom, shape):
             assert_within_tol(other, ref, mag, what + " (band kernel)")
         else:
             assert np.array_equal(y, other), what
+
+
+@pytest.mark.parametrize("k,s", [(3, 1), (3, 2), (2, 2), (5, 1), (7, 1), (9, 1), (13, 1)])
+@pytest.mark.parametrize("shape", [(2, 3, 30, 64), (1, 2, 17, 112), (3, 1, 9, 256), (1, 2, 21, 260), (1, 1, 15, 512), (2, 2, 56, 56)])
+def test_real_cell_average_on_the_row_streaming_kernels(B, k, s, shape):
+    """The average over the cells inside the plane (sws_pool2d_ex, SWS_DIV_REAL_CELLS) for the geometries of the
+    row-streaming kernels, narrow planes and strips, with more and fewer rows of padding below than above; against
+    the oracle and against the band kernel (option pool2d_variant 128)."""
+    p = 0 if k == 2 else k // 2
+    h = shape[2]
+    r = np.random.Generator(np.random.PCG64(k * 10 + s + shape[3]))
+    x = r.standard_normal(shape, dtype=np.float32)
+    for pads in ((p, p, p, p), (p, p, 0, p), (0, p, p, p)):
+        if h + pads[0] + pads[2] < k:
+            continue
+        if k == 2 and pads != (0, 0, 0, 0):
+            continue
+        y = to_host(B.sws_pool2d_ex(0, to_gpu(x), k, k, s, s, pads, B.SWS_DIV_REAL_CELLS, 1.0))
+        ref, mag = oracle.pool2d_ex(0, x, k, k, s, s, pads, True, 1.0)
+        assert_within_tol(y, ref, mag, "real-cell average k=%d s=%d pads=%s %s" % (k, s, pads, shape))
+        B.sws_set_option("pool2d_variant", 128)
+        try:
+            other = to_host(B.sws_pool2d_ex(0, to_gpu(x), k, k, s, s, pads, B.SWS_DIV_REAL_CELLS, 1.0))
+        finally:
+            B.sws_set_option("pool2d_variant", 0)
+        assert_within_tol(other, ref, mag, "band kernel, real-cell average k=%d s=%d pads=%s %s" % (k, s, pads, shape))
