@@ -624,6 +624,18 @@ def run_only(torch, B, workloads, name, steps, cold=False):
         gy = torch.empty(32, 64, ho, ho, device="cuda").normal_()
         gx = torch.empty(32, 64, 112, 112, device="cuda")
         fn = lambda: B.sws_avgpool2d_grad(gy, 112, 112, 3, 3, s, s, 1, 1, 0, 1 / 9, gx=gx)
+    elif name.startswith("poolgrad_"):                    # poolgrad_<max|avg>_<planes>x<h>x<w>_k<k>_s<s>_p<p>: any pooling adjoint
+        _, opn, shp, kn, sn, pn = name.split("_")
+        pl_, h_, w_ = (int(v) for v in shp.split("x"))
+        k, st, pd = int(kn[1:]), int(sn[1:]), int(pn[1:])
+        ho_, wo_ = (h_ + 2 * pd - k) // st + 1, (w_ + 2 * pd - k) // st + 1
+        xw = torch.empty(1, pl_, h_, w_, device="cuda").uniform_(-1, 1)
+        gyw = torch.empty(1, pl_, ho_, wo_, device="cuda").normal_()
+        gxw = torch.empty_like(xw)
+        if opn == "max":
+            fn = lambda: B.sws_maxpool2d_grad(xw, gyw, k, k, st, st, pd, pd, gx=gxw)
+        else:
+            fn = lambda: B.sws_avgpool2d_grad(gyw, h_, w_, k, k, st, st, pd, pd, 0, 1.0 / (k * k), gx=gxw)
     elif name.startswith("widegrad_"):                    # widegrad_<max|avg>_s<s>: adjoints of 3 x 3 pad 1 pooling on x[8,16,512,512]
         _, opn, sn = name.split("_")
         st = int(sn[1:])

@@ -249,6 +249,62 @@ __global__ __launch_bounds__(kWave) void maxpool_grad_rows_kernel(const float *_
 }
 
 // ------------------------------------------------------------------------------------------------
+// Max pooling, 2 x 2 windows at stride 2 without padding: windows do not overlap, a lane's four columns of two
+// rows are two whole windows and nothing comes from a neighbour.  The gradient goes to the first cell
+// (row-major) that holds the window's maximum; rows and windows past the last whole window get 0.
+// ------------------------------------------------------------------------------------------------
+template <int TH>
+__global__ __launch_bounds__(kWave) void maxpool_grad_rows_k2s2_kernel(const float *__restrict__ x, const float *__restrict__ gy,
+                                                                       float *__restrict__ gx, int H, int W, int Ho, int Wo,
+                                                                       int LPR, int G, int lpr_rcp, int nstrips, int64_t planes)
+{
+    static_assert(TH % 2 == 0, "bands of whole windows");
+    Where w;
+    if (!locate(w, LPR, G, lpr_rcp, TH, H, W, nstrips, planes)) return;
+    const int cc = w.inside ? w.c : 0;
+    const float *xp = x + w.plane * (int64_t)H * W + cc;
+    const float *gp = gy + w.plane * (int64_t)Ho * Wo + cc / 2;
+    float *op = gx + w.plane * (int64_t)H * W + cc;
+    v4f xr[TH];
+    v2f g[TH / 2];
+#pragma unroll
+    for (int j = 0; j < TH; ++j) {                                   // all loads in flight together
+        const int row = w.r0 + j;
+        xr[j] = *(const v4f_u *)(xp + (int64_t)(row < H ? row : 0) * W);
+    }
+#pragma unroll
+    for (int i = 0; i < TH / 2; ++i) {
+        const int ho = (w.r0 >> 1) + i;
+        const bool ok = ho < Ho;                                     // (a last odd row belongs to no window)
+        const v2f v = *(const v2f_u *)(gp + (int64_t)(ok ? ho : 0) * Wo);
+        g[i] = ok ? v : (v2f){0.0f, 0.0f};
+    }
+#pragma unroll
+    for (int i = 0; i < TH / 2; ++i) {
+        const float a[4] = {xr[2 * i].x, xr[2 * i].y, xr[2 * i].z, xr[2 * i].w};
+        const float b[4] = {xr[2 * i + 1].x, xr[2 * i + 1].y, xr[2 * i + 1].z, xr[2 * i + 1].w};
+        const float gg[2] = {g[i].x, g[i].y};
+        float oa[4], ob[4];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            float m = a[2 * u];
+            int k = 0;
+            if (a[2 * u + 1] > m) { m = a[2 * u + 1]; k = 1; }
+            if (b[2 * u] > m) { m = b[2 * u]; k = 2; }
+            if (b[2 * u + 1] > m) { k = 3; }
+            oa[2 * u] = k == 0 ? gg[u] : 0.0f;
+            oa[2 * u + 1] = k == 1 ? gg[u] : 0.0f;
+            ob[2 * u] = k == 2 ? gg[u] : 0.0f;
+            ob[2 * u + 1] = k == 3 ? gg[u] : 0.0f;
+        }
+        const int row = w.r0 + 2 * i;
+        if (w.store && row < H) __builtin_nontemporal_store((v4f){oa[0], oa[1], oa[2], oa[3]}, (v4f_u *)(op + (int64_t)row * W));
+        if (w.store && row + 1 < H)
+            __builtin_nontemporal_store((v4f){ob[0], ob[1], ob[2], ob[3]}, (v4f_u *)(op + (int64_t)(row + 1) * W));
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // Average pooling, stride 2 (same bands): a cell adds f * gy over the windows that contain it.
 // ------------------------------------------------------------------------------------------------
 template <int TH>
@@ -293,6 +349,36 @@ __global__ __launch_bounds__(kWave) void avgpool_grad_rows_s2_kernel(const float
     }
 }
 
+// Average pooling, 2 x 2 windows at stride 2 without padding: every cell of a window gets scale * gy of that window;
+// a last odd row gets 0.
+template <int TH>
+__global__ __launch_bounds__(kWave) void avgpool_grad_rows_k2s2_kernel(const float *__restrict__ gy, float *__restrict__ gx,
+                                                                       int H, int W, int Ho, int Wo, int LPR, int G,
+                                                                       int lpr_rcp, int nstrips, int64_t planes, float scale)
+{
+    static_assert(TH % 2 == 0, "bands of whole windows");
+    Where w;
+    if (!locate(w, LPR, G, lpr_rcp, TH, H, W, nstrips, planes)) return;
+    const int cc = w.inside ? w.c : 0;
+    const float *gp = gy + w.plane * (int64_t)Ho * Wo + cc / 2;
+    float *op = gx + w.plane * (int64_t)H * W + cc;
+    v2f g[TH / 2];
+#pragma unroll
+    for (int i = 0; i < TH / 2; ++i) {
+        const int ho = (w.r0 >> 1) + i;
+        const bool ok = ho < Ho;
+        const v2f v = *(const v2f_u *)(gp + (int64_t)(ok ? ho : 0) * Wo);
+        g[i] = ok ? (v2f){v.x * scale, v.y * scale} : (v2f){0.0f, 0.0f};
+    }
+#pragma unroll
+    for (int i = 0; i < TH / 2; ++i) {
+        const v4f o = {g[i].x, g[i].x, g[i].y, g[i].y};
+        const int row = w.r0 + 2 * i;
+        if (w.store && row < H) __builtin_nontemporal_store(o, (v4f_u *)(op + (int64_t)row * W));
+        if (w.store && row + 1 < H) __builtin_nontemporal_store(o, (v4f_u *)(op + (int64_t)(row + 1) * W));
+    }
+}
+
 struct RowsGrid {
     int LPR, G, rcp, nstrips;
     dim3 grid;
@@ -333,6 +419,16 @@ hipError_t launch_maxpool2d_grad_rows(const float *x, const float *gy, float *gx
                                       int Wo, int kh, int kw, int sh, int sw, int ph, int pw, hipStream_t s, bool *taken)
 {
     *taken = false;
+    if (kh == 2 && kw == 2 && sh == 2 && sw == 2 && ph == 0 && pw == 0 && !(W & 3) && W >= 4 && H >= 2 && Wo == W / 2 &&
+        Ho == H / 2) {
+        constexpr int TH = 4;
+        const RowsGrid r = rows_grid(planes, H, W, TH);
+        if (!r.ok) return hipSuccess;
+        *taken = true;
+        hipLaunchKernelGGL((maxpool_grad_rows_k2s2_kernel<TH>), r.grid, dim3(kWave), 0, s, x, gy, gx, H, W, Ho, Wo, r.LPR, r.G,
+                           r.rcp, r.nstrips, planes);
+        return hipGetLastError();
+    }
     if (!rows_shape(H, W, Ho, Wo, kh, kw, sh, sw, ph, pw)) return hipSuccess;
     constexpr int TH1 = 4, TH2 = 4;
     const RowsGrid r = rows_grid(planes, H, W, sh == 1 ? TH1 : TH2);
@@ -351,6 +447,16 @@ hipError_t launch_avgpool2d_grad_rows(const float *gy, float *gx, int64_t planes
                                       int kw, int sh, int sw, int ph, int pw, float scale, hipStream_t s, bool *taken)
 {
     *taken = false;
+    if (kh == 2 && kw == 2 && sh == 2 && sw == 2 && ph == 0 && pw == 0 && !(W & 3) && W >= 4 && H >= 2 && Wo == W / 2 &&
+        Ho == H / 2) {
+        constexpr int TH2 = 4;
+        const RowsGrid r = rows_grid(planes, H, W, TH2);
+        if (!r.ok) return hipSuccess;
+        *taken = true;
+        hipLaunchKernelGGL((avgpool_grad_rows_k2s2_kernel<TH2>), r.grid, dim3(kWave), 0, s, gy, gx, H, W, Ho, Wo, r.LPR, r.G,
+                           r.rcp, r.nstrips, planes, scale);
+        return hipGetLastError();
+    }
     if (sh != 2 || !rows_shape(H, W, Ho, Wo, kh, kw, sh, sw, ph, pw)) return hipSuccess;
     constexpr int TH = 4;
     const RowsGrid r = rows_grid(planes, H, W, TH);

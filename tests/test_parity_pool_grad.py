@@ -229,3 +229,47 @@ def test_row_streaming_adjoints_guard_band(B):
             fn(buf[128:128 + n].view(3, 3, 21, wdt))
             torch.cuda.synchronize()
             assert bool((buf[:128] == 7.0).all()) and bool((buf[128 + n:] == 7.0).all())
+
+
+@pytest.mark.parametrize("variant", [0, 128])
+@pytest.mark.parametrize("shape", [(1, 1, 2, 4), (2, 5, 7, 12), (1, 9, 9, 60), (3, 3, 37, 112), (1, 2, 112, 256), (1, 17, 6, 20),
+                                   (2, 2, 56, 56), (1, 3, 21, 260), (1, 2, 10, 480), (1, 1, 15, 1000)])
+def test_row_streaming_maxpool_grad_2x2_stride_2(B, shape, variant):
+    """2 x 2 windows at stride 2 without padding (windows do not overlap): odd heights (a last row without a window),
+    narrow planes and strips; random data within tolerance, ties with integer gradients bit for bit, and the
+    gradients of a plane add up to what came in.  variant 128 runs the same cases on the band kernel."""
+    h, wd = shape[2], shape[3]
+    geom = (2, 2, 2, 2, 0, 0)
+    ho, wo = (h - 2) // 2 + 1, (wd - 2) // 2 + 1
+    r = np.random.Generator(np.random.PCG64(h * 1000 + wd))
+    x = r.standard_normal(shape, dtype=np.float32)
+    gy = r.standard_normal(shape[:2] + (ho, wo), dtype=np.float32)
+    xi = workloads.integer_valued(shape, 0, 2, h + wd)
+    gi = workloads.integer_valued(shape[:2] + (ho, wo), -3, 3, h * wd)
+    B.sws_set_option("pool2d_variant", variant)
+    try:
+        _check(B, x, gy, geom, "rows max grad 2x2 %s" % (shape,))
+        gx, ref = _check(B, xi, gi, geom, "rows max grad 2x2, ties %s" % (shape,))
+    finally:
+        B.sws_set_option("pool2d_variant", 0)
+    assert np.array_equal(gx.astype(np.float64), ref)
+    assert np.array_equal(gx.astype(np.float64).sum(axis=(2, 3)), gi.astype(np.float64).sum(axis=(2, 3)))
+
+
+@pytest.mark.parametrize("variant", [0, 128])
+@pytest.mark.parametrize("shape", [(1, 1, 2, 4), (2, 5, 7, 12), (3, 3, 37, 112), (1, 2, 112, 256), (2, 2, 56, 56), (1, 3, 21, 260),
+                                   (1, 1, 15, 1000)])
+def test_row_streaming_avgpool_grad_2x2_stride_2(B, shape, variant):
+    h, wd = shape[2], shape[3]
+    geom = (2, 2, 2, 2, 0, 0)
+    ho, wo = (h - 2) // 2 + 1, (wd - 2) // 2 + 1
+    r = np.random.Generator(np.random.PCG64(h * 1000 + wd + 3))
+    gy = r.standard_normal(shape[:2] + (ho, wo), dtype=np.float32)
+    gi = workloads.integer_valued(shape[:2] + (ho, wo), -3, 3, h * wd + 1)
+    B.sws_set_option("pool2d_variant", variant)
+    try:
+        _check_avg(B, gy, h, wd, geom, 0, 0.25, "rows avg grad 2x2 %s" % (shape,))
+        gx, ref = _check_avg(B, gi, h, wd, geom, 0, 0.5, "rows avg grad 2x2, integers %s" % (shape,))
+    finally:
+        B.sws_set_option("pool2d_variant", 0)
+    assert np.array_equal(gx.astype(np.float64), ref)
