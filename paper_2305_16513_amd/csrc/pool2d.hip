@@ -613,7 +613,10 @@ hipError_t launch_rows(const T *x, T *y, int64_t planes, int H, int W, int Ho, i
 // launch order and run on one XCD, so the overlap is read from the L2 that fetched it.
 constexpr int kStripCols = 240, kStripHalo = 8;
 
-template <int OP, int K, int S, int PW, int TH, typename T>
+// RAG: rows whose length is not a multiple of 4 (stride 1).  The lane whose four columns straddle the end of the row
+// loads the row's last four elements instead and moves the ones that are its own to the front (once per output row,
+// after the sums down the columns); its outputs leave one by one.  Rows then start off the 16-byte boundaries.
+template <int OP, int K, int S, int PW, int TH, typename T, bool RAG = false>
 __global__ __launch_bounds__(kWave) void pool2d_rows_wide_kernel(const T *__restrict__ x, T *__restrict__ y, int H, int W,
                                                                  int Ho, int Wo, int ph, int nstrips, int64_t planes,
                                                                  float scale, int div_valid)
@@ -625,6 +628,7 @@ __global__ __launch_bounds__(kWave) void pool2d_rows_wide_kernel(const T *__rest
     constexpr int NOUT = (S == 1) ? 4 : 2;
     constexpr int NR = (TH - 1) * S + K;
     static_assert(NL <= kStripHalo && NRT <= kStripHalo, "windows reach no further than the lanes a strip gives away");
+    static_assert(!RAG || S == 1, "ragged rows: stride 1");
     const int lane = threadIdx.x;
     const int sl = (int)(blockIdx.x >> 3);                          // (band, strip) of the plane
     const int64_t plane = (int64_t)blockIdx.y * kXcd + (blockIdx.x & 7);
@@ -634,7 +638,9 @@ __global__ __launch_bounds__(kWave) void pool2d_rows_wide_kernel(const T *__rest
     if (ho0 >= Ho) return;
     const int c = strip * kStripCols - kStripHalo + 4 * lane;       // my four columns (a multiple of 4: wholly in or out)
     const bool in_cols = c >= 0 && c < W;
-    const T *xp = x + plane * (int64_t)H * W + (in_cols ? c : 0);
+    const int nv = RAG ? W - c : 4;                                  // my columns inside the row: 1 .. 3 for the straddling lane
+    const bool part = RAG && in_cols && nv < 4;
+    const T *xp = x + plane * (int64_t)H * W + (in_cols ? (part ? W - 4 : c) : 0);
     const v4f id4 = {O::id(), O::id(), O::id(), O::id()};
     v4f r[NR];
 #pragma unroll
@@ -665,6 +671,11 @@ __global__ __launch_bounds__(kWave) void pool2d_rows_wide_kernel(const T *__rest
                 v.x = O::f(v.x, r[i * S + a].x); v.y = O::f(v.y, r[i * S + a].y);
                 v.z = O::f(v.z, r[i * S + a].z); v.w = O::f(v.w, r[i * S + a].w);
             }
+        }
+        if constexpr (RAG) {                                         // the straddling lane: its nv elements to the front
+            const float idv = O::id();
+            const v4f m1 = {v.y, v.z, v.w, idv}, m2 = {v.z, v.w, idv, idv}, m3 = {v.w, idv, idv, idv};
+            v = !part ? v : (nv == 3 ? m1 : (nv == 2 ? m2 : m3));
         }
         e[NL] = v.x; e[NL + 1] = v.y; e[NL + 2] = v.z; e[NL + 3] = v.w;
         // (the lanes that store have both neighbours inside the wavefront, holding real columns or the identity)
@@ -705,7 +716,11 @@ __global__ __launch_bounds__(kWave) void pool2d_rows_wide_kernel(const T *__rest
             }
         }
         if (mine && ho < Ho) {
-            if constexpr (NOUT == 4) IO::store4(yp + (int64_t)ho * Wo, (v4f){o[0], o[1], o[2], o[3]}, false);
+            if (part) {
+#pragma unroll
+                for (int cc = 0; cc < NOUT; ++cc)
+                    if (cc < nv) IO::store1_nt(yp + (int64_t)ho * Wo + cc, o[cc]);
+            } else if constexpr (NOUT == 4) IO::store4(yp + (int64_t)ho * Wo, (v4f){o[0], o[1], o[2], o[3]}, false);
             else IO::store2_nt(yp + (int64_t)ho * Wo, (v2f){o[0], o[1]});
         }
     }
@@ -715,6 +730,19 @@ template <int OP, int K, int S, int PW, int TH, typename T>
 hipError_t launch_rows_wide(const T *x, T *y, int64_t planes, int H, int W, int Ho, int Wo, int ph, float scale,
                             int div_valid, hipStream_t s, bool *taken)
 {
+    if constexpr (S == 1) {
+        if (W & 3) {                                                 // ragged rows
+            const int nstrips = (W + kStripCols - 1) / kStripCols;
+            const int bands = (Ho + TH - 1) / TH;
+            const int64_t spp = (int64_t)bands * nstrips;
+            const int64_t rounds = (planes + kXcd - 1) / kXcd;
+            *taken = rounds <= 65535 && spp * kXcd <= 2147483647LL;
+            if (!*taken) return hipSuccess;
+            hipLaunchKernelGGL((pool2d_rows_wide_kernel<OP, K, S, PW, TH, T, true>), dim3((unsigned)(spp * kXcd), (unsigned)rounds),
+                               dim3(kWave), 0, s, x, y, H, W, Ho, Wo, ph, nstrips, planes, scale, div_valid);
+            return hipGetLastError();
+        }
+    }
     const int nstrips = (W + kStripCols - 1) / kStripCols;
     const int bands = (Ho + TH - 1) / TH;
     const int64_t spp = (int64_t)bands * nstrips;                    // wavefronts per plane
@@ -736,8 +764,19 @@ hipError_t dispatch_rows(const T *x, T *y, int64_t planes, int H, int W, int Ho,
                          int sw, int ph, int pw, float scale, int div_valid, hipStream_t s, bool *taken)
 {
     *taken = false;
-    if (kh != kw || sh != sw || (W & 3) || W < 4 || ph < 0 || ph >= kh || (g_opt.pool2d_variant & 128))
+    if (kh != kw || sh != sw || W < 4 || ph < 0 || ph >= kh || (g_opt.pool2d_variant & 128)) return hipSuccess;
+    if (W & 3) {
+        // rows that are not a multiple of 4 long: the strip form at stride 1, from 64 columns on (narrower planes: too many
+        // lanes on partial groups)
+        if (sh != 1 || W < 64 || Wo != W) return hipSuccess;
+        if (kh == 3 && pw == 1) return launch_rows_wide<OP, 3, 1, 1, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
+        if (kh == 5 && pw == 2) return launch_rows_wide<OP, 5, 1, 2, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
+        if (kh == 7 && pw == 3) return launch_rows_wide<OP, 7, 1, 3, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
+        if (kh == 9 && pw == 4) return launch_rows_wide<OP, 9, 1, 4, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
+        if (kh == 11 && pw == 5) return launch_rows_wide<OP, 11, 1, 5, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
+        if (kh == 13 && pw == 6) return launch_rows_wide<OP, 13, 1, 6, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
         return hipSuccess;
+    }
     if (W > 256) {                                   // strips of 256 columns
         if (kh == 3 && sh == 1 && pw == 1 && Wo == W)
             return launch_rows_wide<OP, 3, 1, 1, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);

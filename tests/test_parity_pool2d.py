@@ -372,3 +372,45 @@ def test_real_cell_average_on_the_row_streaming_kernels(B, k, s, shape):
         finally:
             B.sws_set_option("pool2d_variant", 0)
         assert_within_tol(other, ref, mag, "band kernel, real-cell average k=%d s=%d pads=%s %s" % (k, s, pads, shape))
+
+
+@pytest.mark.parametrize("op", ["add", "max", "min"])
+@pytest.mark.parametrize("k", [3, 5, 7, 9, 11, 13])
+@pytest.mark.parametrize("shape", [(2, 3, 19, 65), (1, 2, 30, 111), (1, 9, 9, 149), (1, 1, 12, 255), (2, 1, 7, 257), (1, 2, 10, 301),
+                                   (1, 1, 6, 483), (1, 1, 5, 242)])
+def test_row_streaming_kernel_on_rows_not_a_multiple_of_4_long(B, op, k, shape):
+    """Stride-1 windows on rows of 65 .. 483 elements with every remainder mod 4: the lane that straddles the end of a
+    row takes the row's last four elements and keeps its own; rows start off the 16-byte boundaries.  Against the
+    oracle (also the real-cell average) and against the band kernel; guard elements around y."""
+    import torch
+    p = k // 2
+    n, c, h, w = shape
+    rng = np.random.Generator(np.random.PCG64(3000 * k + h * w + n))
+    x = rng.standard_normal(shape, dtype=np.float32)
+    scale = 1.0 / (k * k)
+    for ph in sorted({p, 0}):
+        if h + 2 * ph < k:
+            continue
+        ho = h + 2 * ph - k + 1
+        buf = torch.full((n * c * ho * w + 64,), 4321.0, device="cuda")
+        yv = buf[32:32 + n * c * ho * w].view(n, c, ho, w)
+        B.sws_pool2d(OPS[op], to_gpu(x), k, k, 1, 1, ph, p, scale, y=yv)
+        y = to_host(yv)
+        ref, mag = oracle.pool2d(OPS[op], x, k, k, 1, 1, ph, p, scale)
+        what = "ragged rows %s k=%d ph=%d %s" % (op, k, ph, shape)
+        if op == "add":
+            assert_within_tol(y, ref, mag, what)
+        else:
+            assert_bit_exact(y, ref, what)
+        assert bool((buf[:32] == 4321.0).all()) and bool((buf[32 + n * c * ho * w:] == 4321.0).all()), what
+        B.sws_set_option("pool2d_variant", 128)
+        try:
+            other = to_host(B.sws_pool2d(OPS[op], to_gpu(x), k, k, 1, 1, ph, p, scale))
+        finally:
+            B.sws_set_option("pool2d_variant", 0)
+        if op != "add":
+            assert np.array_equal(y, other), what
+    if op == "add":
+        yr = to_host(B.sws_pool2d_ex(0, to_gpu(x), k, k, 1, 1, (p, p, p, p), B.SWS_DIV_REAL_CELLS, 1.0))
+        ref, mag = oracle.pool2d_ex(0, x, k, k, 1, 1, (p, p, p, p), True, 1.0)
+        assert_within_tol(yr, ref, mag, "ragged rows, real-cell average k=%d %s" % (k, shape))
