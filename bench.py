@@ -321,7 +321,53 @@ def sweeps_table(torch, B, workloads, iters=20):
             out["same_size_pooling"]["cfg3_%s_%dx%d_s%d_mirror" % (opn, k, k, st)] = {
                 "ms": round(ms, 4), "GBps": round(nb / ms / 1e6, 1), "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
             del y
+    # larger centred windows on the same planes (plain and mirrored), warm like the rows above
+    for opn, op, k, mode in (("avg", 0, 9, None), ("avg", 0, 13, None), ("max", 1, 13, None), ("avg", 0, 13, B.SWS_PAD_MIRROR)):
+        y = torch.empty(32, 64, 112, 112, device="cuda")
+        if mode is None:
+            fn = lambda: B.sws_pool2d(op, x3, k, k, 1, 1, k // 2, k // 2, 1.0 / (k * k), y=y)
+        else:
+            fn = lambda: B.sws_pool2d_padded(op, x3, k, k, 1, 1, (k // 2,) * 4, mode, 1.0 / (k * k), y=y)
+        ms = time_launches(torch, fn, iters)
+        nb = 4 * (x3.numel() + y.numel())
+        out["same_size_pooling"]["cfg3_%s_%dx%d_s1%s" % (opn, k, k, "" if mode is None else "_mirror")] = {
+            "ms": round(ms, 4), "GBps": round(nb / ms / 1e6, 1), "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+        del y
     del x3
+    torch.cuda.empty_cache()
+    # planes wider than a wavefront's 256 columns and rows that are not a multiple of 4 long (strips), and the adjoints
+    # of 2 x 2 stride-2 pooling
+    out["wide_planes"] = {}
+    xw = torch.empty(8, 16, 512, 512, device="cuda").uniform_(-1, 1)
+    yw = torch.empty_like(xw)
+    gxw = torch.empty_like(xw)
+    nb2 = 8.0 * xw.numel()
+    for name, fn, nb in (("512x512_avg_3x3_s1", lambda: B.sws_pool2d(0, xw, 3, 3, 1, 1, 1, 1, 1 / 9, y=yw), nb2),
+                         ("512x512_max_7x7_s1", lambda: B.sws_pool2d(1, xw, 7, 7, 1, 1, 3, 3, 1.0, y=yw), nb2),
+                         ("512x512_avg_3x3_s1_mirror",
+                          lambda: B.sws_pool2d_padded(0, xw, 3, 3, 1, 1, (1, 1, 1, 1), B.SWS_PAD_MIRROR, 1 / 9, y=yw), nb2),
+                         ("512x512_maxpool3x3_s1_grad", lambda: B.sws_maxpool2d_grad(xw, yw, 3, 3, 1, 1, 1, 1, gx=gxw), 1.5 * nb2)):
+        ms = time_launches(torch, fn, iters)
+        out["wide_planes"][name] = {"us": round(ms * 1e3, 2), "GBps": round(nb / ms / 1e6, 1),
+                                    "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+    del xw, yw, gxw
+    xr_ = torch.empty(32, 64, 111, 111, device="cuda").uniform_(-1, 1)
+    yr_ = torch.empty_like(xr_)
+    ms = time_launches(torch, lambda: B.sws_pool2d(1, xr_, 3, 3, 1, 1, 1, 1, 1.0, y=yr_), iters)
+    out["wide_planes"]["111x111_max_3x3_s1"] = {"us": round(ms * 1e3, 2), "GBps": round(8.0 * xr_.numel() / ms / 1e6, 1),
+                                                "frac_hbm": round(8.0 * xr_.numel() / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+    del xr_, yr_
+    x3b = torch.empty(32, 64, 112, 112, device="cuda").uniform_(-1, 1)
+    gy3b = torch.empty(32, 64, 56, 56, device="cuda").normal_()
+    gx3b = torch.empty_like(x3b)
+    for name, fn, nb in (("cfg3_maxpool2x2_s2_grad", lambda: B.sws_maxpool2d_grad(x3b, gy3b, 2, 2, 2, 2, 0, 0, gx=gx3b),
+                          4.0 * (2 * x3b.numel() + gy3b.numel())),
+                         ("cfg3_avgpool2x2_s2_grad", lambda: B.sws_avgpool2d_grad(gy3b, 112, 112, 2, 2, 2, 2, 0, 0, 0, 0.25, gx=gx3b),
+                          4.0 * (x3b.numel() + gy3b.numel()))):
+        ms = time_launches(torch, fn, iters)
+        out["wide_planes"][name] = {"us": round(ms * 1e3, 2), "GBps": round(nb / ms / 1e6, 1),
+                                    "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+    del x3b, gy3b, gx3b
     torch.cuda.empty_cache()
     # configuration 5's sliding sums on 16-bit storage (fp32 arithmetic, one rounding): half the bytes
     x16 = g(workloads.make(5)[0]).to(torch.bfloat16)
