@@ -613,7 +613,7 @@ hipError_t launch_rows(const T *x, T *y, int64_t planes, int H, int W, int Ho, i
 // launch order and run on one XCD, so the overlap is read from the L2 that fetched it.
 constexpr int kStripCols = 240, kStripHalo = 8;
 
-// RAG: rows whose length is not a multiple of 4 (stride 1).  The lane whose four columns straddle the end of the row
+// RAG: rows whose length is not a multiple of 4.  The lane whose four columns straddle the end of the row
 // loads the row's last four elements instead and moves the ones that are its own to the front (once per output row,
 // after the sums down the columns); its outputs leave one by one.  Rows then start off the 16-byte boundaries.
 template <int OP, int K, int S, int PW, int TH, typename T, bool RAG = false>
@@ -628,7 +628,6 @@ __global__ __launch_bounds__(kWave) void pool2d_rows_wide_kernel(const T *__rest
     constexpr int NOUT = (S == 1) ? 4 : 2;
     constexpr int NR = (TH - 1) * S + K;
     static_assert(NL <= kStripHalo && NRT <= kStripHalo, "windows reach no further than the lanes a strip gives away");
-    static_assert(!RAG || S == 1, "ragged rows: stride 1");
     const int lane = threadIdx.x;
     const int sl = (int)(blockIdx.x >> 3);                          // (band, strip) of the plane
     const int64_t plane = (int64_t)blockIdx.y * kXcd + (blockIdx.x & 7);
@@ -716,10 +715,13 @@ __global__ __launch_bounds__(kWave) void pool2d_rows_wide_kernel(const T *__rest
             }
         }
         if (mine && ho < Ho) {
-            if (part) {
+            // the outputs of mine that exist: all of them except at the end of a row (a straddling lane; at stride 2 a
+            // last window that would pass the end of the plane)
+            const int n_ok = Wo - (S == 1 ? c : c / 2);
+            if (n_ok < NOUT) {
 #pragma unroll
                 for (int cc = 0; cc < NOUT; ++cc)
-                    if (cc < nv) IO::store1_nt(yp + (int64_t)ho * Wo + cc, o[cc]);
+                    if (cc < n_ok) IO::store1_nt(yp + (int64_t)ho * Wo + cc, o[cc]);
             } else if constexpr (NOUT == 4) IO::store4(yp + (int64_t)ho * Wo, (v4f){o[0], o[1], o[2], o[3]}, false);
             else IO::store2_nt(yp + (int64_t)ho * Wo, (v2f){o[0], o[1]});
         }
@@ -730,7 +732,7 @@ template <int OP, int K, int S, int PW, int TH, typename T>
 hipError_t launch_rows_wide(const T *x, T *y, int64_t planes, int H, int W, int Ho, int Wo, int ph, float scale,
                             int div_valid, hipStream_t s, bool *taken)
 {
-    if constexpr (S == 1) {
+    {
         if (W & 3) {                                                 // ragged rows
             const int nstrips = (W + kStripCols - 1) / kStripCols;
             const int bands = (Ho + TH - 1) / TH;
@@ -766,9 +768,21 @@ hipError_t dispatch_rows(const T *x, T *y, int64_t planes, int H, int W, int Ho,
     *taken = false;
     if (kh != kw || sh != sw || W < 4 || ph < 0 || ph >= kh || (g_opt.pool2d_variant & 128)) return hipSuccess;
     if (W & 3) {
-        // rows that are not a multiple of 4 long: the strip form at stride 1, from 64 columns on (narrower planes: too many
-        // lanes on partial groups)
-        if (sh != 1 || W < 64 || Wo != W) return hipSuccess;
+        // rows that are not a multiple of 4 long: the strip form, from 64 columns on (narrower planes: too many lanes on
+        // partial groups).  Stride 2 with and without padding (3 x 3 without: the classic "valid" pooling).  Cold,
+        // strips / band kernel: [2048,111,111] 3 x 3 stride 2 29.8 / 50.0 us, [1024,149,149] 21.7 / 48.1 us; on rows that
+        // are a multiple of 4 long the band kernel's own 3 x 3 stride-2 instances are level or ahead (28.8 / 24.1 us).
+        if (W < 64) return hipSuccess;
+        if (sh == 2) {
+            if (Wo != (W + 2 * pw - kh) / 2 + 1) return hipSuccess;
+            if (kh == 3 && pw <= 1) {
+                if (pw == 1) return launch_rows_wide<OP, 3, 2, 1, 1, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
+                return launch_rows_wide<OP, 3, 2, 0, 1, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
+            }
+            if (kh == 2 && pw == 0) return launch_rows_wide<OP, 2, 2, 0, 1, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
+            return hipSuccess;
+        }
+        if (sh != 1 || Wo != W) return hipSuccess;
         if (kh == 3 && pw == 1) return launch_rows_wide<OP, 3, 1, 1, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
         if (kh == 5 && pw == 2) return launch_rows_wide<OP, 5, 1, 2, 2, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
         if (kh == 7 && pw == 3) return launch_rows_wide<OP, 7, 1, 3, 4, T>(x, y, planes, H, W, Ho, Wo, ph, scale, div_valid, s, taken);
