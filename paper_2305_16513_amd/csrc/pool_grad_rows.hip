@@ -1,7 +1,7 @@
-// Adjoints of 3 x 3 pooling (one column of padding, stride 1 or 2) on planes whose rows fit a
-// wavefront — the backward passes of the row-streaming pooling kernel (Section 2.3 used for
-// training), without LDS.  W a multiple of 4 (beyond 256 columns: strips, see locate()); stride 1: Wo = W,
-// stride 2: Wo = W / 2.
+// Adjoints of 3 x 3 pooling (stride 1 with one column of padding, stride 2 with one or none) and of 2 x 2
+// pooling at stride 2 — the backward passes of the row-streaming pooling kernel (Section 2.3 used for
+// training), without LDS.  Rows of up to 256 columns fit a wavefront, wider ones go in strips (see locate());
+// rows that are not a multiple of 4 long end in a lane that holds fewer than four columns (see Cols).
 //
 // As in the forward kernel a lane owns four adjacent columns, the W/4 lanes of a group move a row as
 // one contiguous run of 128-bit accesses, the G = 64 / (W/4) groups of a wavefront take G consecutive
@@ -80,15 +80,63 @@ __device__ __forceinline__ bool locate(Where &w, int LPR, int G, int lpr_rcp, in
     return true;
 }
 
+// A lane's columns in memory.  Rows whose length is not a multiple of 4 (RAG) end inside a lane: that lane
+// (part) reads the row's last four elements instead of its own four and shifts them down, so that every lane
+// still issues one 128-bit load per row, and writes its nv < 4 columns one by one.
+struct Cols {
+    int cx;                 // column at which the lane's load starts
+    int nv;                 // columns of mine that exist (meaningful where part)
+    bool part;
+};
+template <bool RAG>
+__device__ __forceinline__ Cols columns(const Where &w, int W)
+{
+    Cols k;
+    k.part = RAG && w.inside && w.c + 4 > W;
+    k.nv = W - w.c;
+    k.cx = !w.inside ? 0 : k.part ? W - 4 : w.c;     // (lanes outside the plane read column 0 and drop it)
+    return k;
+}
+template <bool RAG>
+__device__ __forceinline__ v4f load4(const float *row, const Cols &k, float fill)
+{
+    v4f v = *(const v4f_u *)(row + k.cx);
+    if constexpr (RAG) {
+        const float a = k.nv == 1 ? v.w : k.nv == 2 ? v.z : v.y;
+        const float b = k.nv == 1 ? fill : k.nv == 2 ? v.w : v.z;
+        const float c = k.nv == 3 ? v.w : fill;
+        if (k.part) v = (v4f){a, b, c, fill};
+    }
+    return v;
+}
+template <bool RAG>
+__device__ __forceinline__ void store4(float *p, const float (&o)[4], const Cols &k)
+{
+    if (!RAG || !k.part) {
+        __builtin_nontemporal_store((v4f){o[0], o[1], o[2], o[3]}, (v4f_u *)p);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 3; ++e)
+            if (e < k.nv) p[e] = o[e];
+    }
+}
+// Window columns wo0, wo0 + 1 of a gy row at stride 2; those beyond the row's end read as 0.
+__device__ __forceinline__ void load_windows2(const float *row, int wo0, int Wo, bool ok, float &g0, float &g1)
+{
+    const float a = row[wo0 < Wo ? wo0 : Wo - 1], b = row[wo0 + 1 < Wo ? wo0 + 1 : Wo - 1];
+    g0 = (ok && wo0 < Wo) ? a : 0.0f;
+    g1 = (ok && wo0 + 1 < Wo) ? b : 0.0f;
+}
+
 // One x row -> for each of the lane's NW window columns the maximum of its three cells (hm) and the
 // number of the first cell holding it (hc), numbers being base + (column among e[0..5]).
-// STEP = 1: windows u = 0..3 see e[u .. u+2]; STEP = 2: windows u = 0, 1 see e[2u .. 2u+2].
-template <int STEP, int NW>
+// STEP = 1: windows u = 0..3 see e[u .. u+2]; STEP = 2: windows u = 0, 1 see e[OFF + 2u .. OFF + 2u+2].
+template <int STEP, int NW, int OFF>
 __device__ __forceinline__ void row_maxima(const float (&e)[6], int base, float (&hm)[NW], int (&hc)[NW])
 {
 #pragma unroll
     for (int u = 0; u < NW; ++u) {
-        const int c = STEP * u;
+        const int c = STEP * u + OFF;
         float m = e[c];
         int k = base + c;
         if (e[c + 1] > m) { m = e[c + 1]; k = base + c + 1; }
@@ -110,29 +158,36 @@ __device__ __forceinline__ void row_maxima(const float (&e)[6], int base, float 
 //          over e[0..5] = columns 4l - 1 .. 4l + 4; cell v (column 4l + v, e[v + 1]) lies in windows
 //          v - 1, v, v + 1, of which u = -1 is the previous lane's u = 3 (where the cell is e[5]) and
 //          u = 4 the next lane's u = 0 (where it is e[0]).
-//          S = 2: window wo covers columns 2 wo - 1 .. 2 wo + 1; the lane's windows are wo = 2l + u, u < 2,
+//          S = 2, PW = 1: window wo covers columns 2 wo - 1 .. 2 wo + 1; the lane's windows are wo = 2l + u, u < 2,
 //          over e[0..4]; cell 0 lies in window 0, cell 1 in 0 and 1, cell 2 in 1, cell 3 in 1 and in the
 //          next lane's window 0 (where it is e[0]).
+//          S = 2, PW = 0: window wo covers columns 2 wo .. 2 wo + 2, the lane's two windows lie over e[1..5]; cell 0
+//          lies in window 0 and in the previous lane's window 1 (where it is e[5]), cell 1 in 0, cell 2 in 0 and 1,
+//          cell 3 in 1.  Windows beyond the row's last (wo >= Wo) are given gradient 0.
 // ------------------------------------------------------------------------------------------------
-template <int S, int TH>
+template <int S, int TH, int PW, bool RAG>
 __global__ __launch_bounds__(kWave) void maxpool_grad_rows_kernel(const float *__restrict__ x, const float *__restrict__ gy,
                                                                   float *__restrict__ gx, int H, int W, int Ho, int Wo,
                                                                   int ph, int LPR, int G, int lpr_rcp, int nstrips,
                                                                   int64_t planes)
 {
     static_assert(S == 1 || (S == 2 && TH % 2 == 0), "bands of an even number of rows at stride 2");
+    static_assert(PW == 1 || (S == 2 && PW == 0), "stride 1: one column of padding");
     constexpr int NW = S == 1 ? 4 : 2;                               // window columns of a lane
     constexpr int NWR = S == 1 ? TH + 2 : TH / 2 + 1;                // window rows of a band
     constexpr int NXR = S == 1 ? TH + 4 : TH + 3;                    // x rows of a band
+    constexpr int OFF = 1 - PW;                                      // e[] index at which the lane's first window starts
+    constexpr bool kBefore = S == 1 || PW == 1, kAfter = S == 1 || PW == 0;    // the neighbours' columns a lane sees
     const float ninf = -__builtin_huge_valf();
     Where w;
     if (!locate(w, LPR, G, lpr_rcp, TH, H, W, nstrips, planes)) return;
+    const Cols k = columns<RAG>(w, W);
     const int hf = S == 1 ? w.r0 + ph - 2 : (w.r0 + ph - 1) >> 1;    // first window row (may be < 0)
     const int xr0 = S == 1 ? w.r0 - 2 : 2 * hf - ph;                 // first x row (may be < 0)
     const int d0 = S == 1 ? 2 : w.r0 - xr0;                          // cell row t is x row j = d0 + t
-    const int cc = w.inside ? w.c : 0;                               // (lanes outside the plane read column 0 and drop it)
-    const float *xp = x + w.plane * (int64_t)H * W + cc;
-    const float *gp = gy + w.plane * (int64_t)Ho * Wo + (NW == 4 ? cc : cc / 2);
+    const int cc = w.inside ? w.c : 0;
+    const float *xp = x + w.plane * (int64_t)H * W;
+    const float *gp = gy + w.plane * (int64_t)Ho * Wo;
     float *op = gx + w.plane * (int64_t)H * W + cc;
 
     // ---- all loads in flight together; rows and columns outside the plane: -inf cells, zero gradients
@@ -141,7 +196,7 @@ __global__ __launch_bounds__(kWave) void maxpool_grad_rows_kernel(const float *_
     for (int j = 0; j < NXR; ++j) {
         const int row = xr0 + j;
         const bool in_rows = row >= 0 && row < H, ok = in_rows && w.inside;
-        const v4f v = *(const v4f_u *)(xp + (int64_t)(in_rows ? row : 0) * W);
+        const v4f v = load4<RAG>(xp + (int64_t)(in_rows ? row : 0) * W, k, ninf);
         xr[j] = ok ? v : (v4f){ninf, ninf, ninf, ninf};
     }
     float g[NWR][NW];
@@ -150,12 +205,14 @@ __global__ __launch_bounds__(kWave) void maxpool_grad_rows_kernel(const float *_
         const int ho = hf + i;
         const bool in_rows = ho >= 0 && ho < Ho, ok = in_rows && w.inside;
         const float *src = gp + (int64_t)(in_rows ? ho : 0) * Wo;
-        if constexpr (NW == 4) {
-            const v4f v = *(const v4f_u *)src;
+        if constexpr (NW == 4) {                                     // (Wo = W: the same columns as x)
+            const v4f v = load4<RAG>(src, k, 0.0f);
             g[i][0] = ok ? v.x : 0.0f; g[i][1] = ok ? v.y : 0.0f; g[i][2] = ok ? v.z : 0.0f; g[i][3] = ok ? v.w : 0.0f;
-        } else {
-            const v2f v = *(const v2f_u *)src;
+        } else if constexpr (!RAG && PW == 1) {                      // (Wo = W / 2: both windows exist)
+            const v2f v = *(const v2f_u *)(src + cc / 2);
             g[i][0] = ok ? v.x : 0.0f; g[i][1] = ok ? v.y : 0.0f;
+        } else {
+            load_windows2(src, cc / 2, Wo, ok, g[i][0], g[i][1]);
         }
     }
 
@@ -167,18 +224,18 @@ __global__ __launch_bounds__(kWave) void maxpool_grad_rows_kernel(const float *_
 #pragma unroll
     for (int j = 0; j < NXR; ++j) {
         float e[6];
-        e[1] = xr[j].x; e[2] = xr[j].y; e[3] = xr[j].z; e[4] = xr[j].w;
-        const float b = lane_before(xr[j].w);
-        e[0] = w.first ? ninf : b;
-        if constexpr (S == 1) {
+        e[0] = ninf; e[1] = xr[j].x; e[2] = xr[j].y; e[3] = xr[j].z; e[4] = xr[j].w; e[5] = ninf;
+        if constexpr (kBefore) {
+            const float b = lane_before(xr[j].w);
+            e[0] = w.first ? ninf : b;
+        }
+        if constexpr (kAfter) {
             const float a = lane_after(xr[j].x);
             e[5] = w.last ? ninf : a;
-        } else {
-            e[5] = ninf;                                             // (not read)
         }
         float hm[NW];
         int hc[NW];
-        row_maxima<S, NW>(e, 8 * j, hm, hc);
+        row_maxima<S, NW, OFF>(e, 8 * j, hm, hc);
 #pragma unroll
         for (int i = 0; i < NWR; ++i) {
             const int a = j - S * i;                                 // the row's place in window i
@@ -196,22 +253,24 @@ __global__ __launch_bounds__(kWave) void maxpool_grad_rows_kernel(const float *_
             }
         }
     }
-    // ---- the windows beside the lane's: the previous lane's last (S = 1 only) and the next lane's first
+    // ---- the windows beside the lane's: the previous lane's last and the next lane's first, where they reach
+    //      into the lane's columns
     int wn_b[NWR], wn_a[NWR];
     float g_b[NWR], g_a[NWR];
 #pragma unroll
     for (int i = 0; i < NWR; ++i) {
-        if constexpr (S == 1) {
+        wn_b[i] = wn_a[i] = 0;
+        g_b[i] = g_a[i] = 0.0f;
+        if constexpr (S == 1 || PW == 0) {
             wn_b[i] = lane_before(wn[i][NW - 1]);
             const float t = lane_before(g[i][NW - 1]);
             g_b[i] = w.first ? 0.0f : t;
-        } else {
-            wn_b[i] = 0;
-            g_b[i] = 0.0f;
         }
-        wn_a[i] = lane_after(wn[i][0]);
-        const float t = lane_after(g[i][0]);
-        g_a[i] = w.last ? 0.0f : t;
+        if constexpr (S == 1 || PW == 1) {
+            wn_a[i] = lane_after(wn[i][0]);
+            const float t = lane_after(g[i][0]);
+            g_a[i] = w.last ? 0.0f : t;
+        }
     }
     // ---- every cell adds the gradients of the windows that carry its number
 #pragma unroll
@@ -234,17 +293,24 @@ __global__ __launch_bounds__(kWave) void maxpool_grad_rows_kernel(const float *_
                         else acc += (wn[i][u] == me) ? g[i][u] : 0.0f;
                     }
                 }
-            } else {
+            } else if constexpr (PW == 1) {
 #pragma unroll
                 for (int i = 0; i < NWR; ++i) {
                     if (v <= 1) acc += (wn[i][0] == me) ? g[i][0] : 0.0f;
                     if (v >= 1) acc += (wn[i][1] == me) ? g[i][1] : 0.0f;
                     if (v == 3) acc += (wn_a[i] == 8 * (d0 + t) + 0) ? g_a[i] : 0.0f;
                 }
+            } else {
+#pragma unroll
+                for (int i = 0; i < NWR; ++i) {
+                    if (v == 0) acc += (wn_b[i] == 8 * (d0 + t) + 5) ? g_b[i] : 0.0f;
+                    if (v <= 2) acc += (wn[i][0] == me) ? g[i][0] : 0.0f;
+                    if (v >= 2) acc += (wn[i][1] == me) ? g[i][1] : 0.0f;
+                }
             }
             o[v] = acc;
         }
-        if (row < H && w.store) __builtin_nontemporal_store((v4f){o[0], o[1], o[2], o[3]}, (v4f_u *)(op + (int64_t)row * W));
+        if (row < H && w.store) store4<RAG>(op + (int64_t)row * W, o, k);
     }
 }
 
@@ -253,7 +319,7 @@ __global__ __launch_bounds__(kWave) void maxpool_grad_rows_kernel(const float *_
 // rows are two whole windows and nothing comes from a neighbour.  The gradient goes to the first cell
 // (row-major) that holds the window's maximum; rows and windows past the last whole window get 0.
 // ------------------------------------------------------------------------------------------------
-template <int TH>
+template <int TH, bool RAG>
 __global__ __launch_bounds__(kWave) void maxpool_grad_rows_k2s2_kernel(const float *__restrict__ x, const float *__restrict__ gy,
                                                                        float *__restrict__ gx, int H, int W, int Ho, int Wo,
                                                                        int LPR, int G, int lpr_rcp, int nstrips, int64_t planes)
@@ -261,23 +327,31 @@ __global__ __launch_bounds__(kWave) void maxpool_grad_rows_k2s2_kernel(const flo
     static_assert(TH % 2 == 0, "bands of whole windows");
     Where w;
     if (!locate(w, LPR, G, lpr_rcp, TH, H, W, nstrips, planes)) return;
+    const Cols k = columns<RAG>(w, W);
     const int cc = w.inside ? w.c : 0;
-    const float *xp = x + w.plane * (int64_t)H * W + cc;
-    const float *gp = gy + w.plane * (int64_t)Ho * Wo + cc / 2;
+    const float *xp = x + w.plane * (int64_t)H * W;
+    const float *gp = gy + w.plane * (int64_t)Ho * Wo;
     float *op = gx + w.plane * (int64_t)H * W + cc;
     v4f xr[TH];
     v2f g[TH / 2];
 #pragma unroll
     for (int j = 0; j < TH; ++j) {                                   // all loads in flight together
         const int row = w.r0 + j;
-        xr[j] = *(const v4f_u *)(xp + (int64_t)(row < H ? row : 0) * W);
+        xr[j] = load4<RAG>(xp + (int64_t)(row < H ? row : 0) * W, k, 0.0f);
     }
 #pragma unroll
     for (int i = 0; i < TH / 2; ++i) {
         const int ho = (w.r0 >> 1) + i;
         const bool ok = ho < Ho;                                     // (a last odd row belongs to no window)
-        const v2f v = *(const v2f_u *)(gp + (int64_t)(ok ? ho : 0) * Wo);
-        g[i] = ok ? v : (v2f){0.0f, 0.0f};
+        const float *src = gp + (int64_t)(ok ? ho : 0) * Wo;
+        if constexpr (!RAG) {
+            const v2f v = *(const v2f_u *)(src + cc / 2);
+            g[i] = ok ? v : (v2f){0.0f, 0.0f};
+        } else {                                                     // (a last odd column belongs to no window)
+            float g0, g1;
+            load_windows2(src, cc / 2, Wo, ok, g0, g1);
+            g[i] = (v2f){g0, g1};
+        }
     }
 #pragma unroll
     for (int i = 0; i < TH / 2; ++i) {
@@ -288,26 +362,25 @@ __global__ __launch_bounds__(kWave) void maxpool_grad_rows_k2s2_kernel(const flo
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             float m = a[2 * u];
-            int k = 0;
-            if (a[2 * u + 1] > m) { m = a[2 * u + 1]; k = 1; }
-            if (b[2 * u] > m) { m = b[2 * u]; k = 2; }
-            if (b[2 * u + 1] > m) { k = 3; }
-            oa[2 * u] = k == 0 ? gg[u] : 0.0f;
-            oa[2 * u + 1] = k == 1 ? gg[u] : 0.0f;
-            ob[2 * u] = k == 2 ? gg[u] : 0.0f;
-            ob[2 * u + 1] = k == 3 ? gg[u] : 0.0f;
+            int k4 = 0;
+            if (a[2 * u + 1] > m) { m = a[2 * u + 1]; k4 = 1; }
+            if (b[2 * u] > m) { m = b[2 * u]; k4 = 2; }
+            if (b[2 * u + 1] > m) { k4 = 3; }
+            oa[2 * u] = k4 == 0 ? gg[u] : 0.0f;
+            oa[2 * u + 1] = k4 == 1 ? gg[u] : 0.0f;
+            ob[2 * u] = k4 == 2 ? gg[u] : 0.0f;
+            ob[2 * u + 1] = k4 == 3 ? gg[u] : 0.0f;
         }
         const int row = w.r0 + 2 * i;
-        if (w.store && row < H) __builtin_nontemporal_store((v4f){oa[0], oa[1], oa[2], oa[3]}, (v4f_u *)(op + (int64_t)row * W));
-        if (w.store && row + 1 < H)
-            __builtin_nontemporal_store((v4f){ob[0], ob[1], ob[2], ob[3]}, (v4f_u *)(op + (int64_t)(row + 1) * W));
+        if (w.store && row < H) store4<RAG>(op + (int64_t)row * W, oa, k);
+        if (w.store && row + 1 < H) store4<RAG>(op + (int64_t)(row + 1) * W, ob, k);
     }
 }
 
 // ------------------------------------------------------------------------------------------------
 // Average pooling, stride 2 (same bands): a cell adds f * gy over the windows that contain it.
 // ------------------------------------------------------------------------------------------------
-template <int TH>
+template <int TH, int PW, bool RAG>
 __global__ __launch_bounds__(kWave) void avgpool_grad_rows_s2_kernel(const float *__restrict__ gy, float *__restrict__ gx,
                                                                      int H, int W, int Ho, int Wo, int ph, int LPR, int G,
                                                                      int lpr_rcp, int nstrips, int64_t planes, float scale)
@@ -316,10 +389,11 @@ __global__ __launch_bounds__(kWave) void avgpool_grad_rows_s2_kernel(const float
     constexpr int NWR = TH / 2 + 1;
     Where w;
     if (!locate(w, LPR, G, lpr_rcp, TH, H, W, nstrips, planes)) return;
+    const Cols k = columns<RAG>(w, W);
     const int hf = (w.r0 + ph - 1) >> 1;
     const int d0 = w.r0 - (2 * hf - ph);                             // 1 or 2
     const int cc = w.inside ? w.c : 0;
-    const float *gp = gy + w.plane * (int64_t)Ho * Wo + cc / 2;
+    const float *gp = gy + w.plane * (int64_t)Ho * Wo;
     float *op = gx + w.plane * (int64_t)H * W + cc;
     // per window row: the sums along W that the lane's four cells receive
     float c[NWR][4];
@@ -327,11 +401,24 @@ __global__ __launch_bounds__(kWave) void avgpool_grad_rows_s2_kernel(const float
     for (int i = 0; i < NWR; ++i) {
         const int ho = hf + i;
         const bool in_rows = ho >= 0 && ho < Ho, ok = in_rows && w.inside;
-        const v2f v = *(const v2f_u *)(gp + (int64_t)(in_rows ? ho : 0) * Wo);
-        const float g0 = ok ? v.x * scale : 0.0f, g1 = ok ? v.y * scale : 0.0f;
-        const float t = lane_after(g0);
-        const float ga = w.last ? 0.0f : t;
-        c[i][0] = g0; c[i][1] = g0 + g1; c[i][2] = g1; c[i][3] = g1 + ga;
+        const float *src = gp + (int64_t)(in_rows ? ho : 0) * Wo;
+        float g0, g1;
+        if constexpr (!RAG && PW == 1) {
+            const v2f v = *(const v2f_u *)(src + cc / 2);
+            g0 = ok ? v.x : 0.0f; g1 = ok ? v.y : 0.0f;
+        } else {
+            load_windows2(src, cc / 2, Wo, ok, g0, g1);
+        }
+        g0 *= scale; g1 *= scale;
+        if constexpr (PW == 1) {                                     // windows over columns 2 wo - 1 .. 2 wo + 1
+            const float t = lane_after(g0);
+            const float ga = w.last ? 0.0f : t;
+            c[i][0] = g0; c[i][1] = g0 + g1; c[i][2] = g1; c[i][3] = g1 + ga;
+        } else {                                                     // windows over columns 2 wo .. 2 wo + 2
+            const float t = lane_before(g1);
+            const float gb = w.first ? 0.0f : t;
+            c[i][0] = gb + g0; c[i][1] = g0; c[i][2] = g0 + g1; c[i][3] = g1;
+        }
     }
 #pragma unroll
     for (int t = 0; t < TH; ++t) {
@@ -345,13 +432,13 @@ __global__ __launch_bounds__(kWave) void avgpool_grad_rows_s2_kernel(const float
             for (int i = 0; i < NWR; ++i) acc += (2 * i <= j && j <= 2 * i + 2) ? c[i][v] : 0.0f;
             o[v] = acc;
         }
-        if (row < H && w.store) __builtin_nontemporal_store((v4f){o[0], o[1], o[2], o[3]}, (v4f_u *)(op + (int64_t)row * W));
+        if (row < H && w.store) store4<RAG>(op + (int64_t)row * W, o, k);
     }
 }
 
 // Average pooling, 2 x 2 windows at stride 2 without padding: every cell of a window gets scale * gy of that window;
-// a last odd row gets 0.
-template <int TH>
+// a last odd row or column gets 0.
+template <int TH, bool RAG>
 __global__ __launch_bounds__(kWave) void avgpool_grad_rows_k2s2_kernel(const float *__restrict__ gy, float *__restrict__ gx,
                                                                        int H, int W, int Ho, int Wo, int LPR, int G,
                                                                        int lpr_rcp, int nstrips, int64_t planes, float scale)
@@ -359,23 +446,31 @@ __global__ __launch_bounds__(kWave) void avgpool_grad_rows_k2s2_kernel(const flo
     static_assert(TH % 2 == 0, "bands of whole windows");
     Where w;
     if (!locate(w, LPR, G, lpr_rcp, TH, H, W, nstrips, planes)) return;
+    const Cols k = columns<RAG>(w, W);
     const int cc = w.inside ? w.c : 0;
-    const float *gp = gy + w.plane * (int64_t)Ho * Wo + cc / 2;
+    const float *gp = gy + w.plane * (int64_t)Ho * Wo;
     float *op = gx + w.plane * (int64_t)H * W + cc;
     v2f g[TH / 2];
 #pragma unroll
     for (int i = 0; i < TH / 2; ++i) {
         const int ho = (w.r0 >> 1) + i;
         const bool ok = ho < Ho;
-        const v2f v = *(const v2f_u *)(gp + (int64_t)(ok ? ho : 0) * Wo);
-        g[i] = ok ? (v2f){v.x * scale, v.y * scale} : (v2f){0.0f, 0.0f};
+        const float *src = gp + (int64_t)(ok ? ho : 0) * Wo;
+        if constexpr (!RAG) {
+            const v2f v = *(const v2f_u *)(src + cc / 2);
+            g[i] = ok ? (v2f){v.x * scale, v.y * scale} : (v2f){0.0f, 0.0f};
+        } else {
+            float g0, g1;
+            load_windows2(src, cc / 2, Wo, ok, g0, g1);
+            g[i] = (v2f){g0 * scale, g1 * scale};
+        }
     }
 #pragma unroll
     for (int i = 0; i < TH / 2; ++i) {
-        const v4f o = {g[i].x, g[i].x, g[i].y, g[i].y};
+        const float o[4] = {g[i].x, g[i].x, g[i].y, g[i].y};
         const int row = w.r0 + 2 * i;
-        if (w.store && row < H) __builtin_nontemporal_store(o, (v4f_u *)(op + (int64_t)row * W));
-        if (w.store && row + 1 < H) __builtin_nontemporal_store(o, (v4f_u *)(op + (int64_t)(row + 1) * W));
+        if (w.store && row < H) store4<RAG>(op + (int64_t)row * W, o, k);
+        if (w.store && row + 1 < H) store4<RAG>(op + (int64_t)(row + 1) * W, o, k);
     }
 }
 
@@ -395,7 +490,7 @@ RowsGrid rows_grid(int64_t planes, int H, int W, int TH)
         r.nstrips = (W + kStripCols - 1) / kStripCols;
         spp = (int64_t)bands * r.nstrips;
     } else {
-        r.LPR = W / 4;
+        r.LPR = (W + 3) / 4;                                         // (a last lane may hold fewer than 4 columns)
         r.G = kWave / r.LPR;
         r.rcp = (65536 + r.LPR - 1) / r.LPR;
         r.nstrips = 0;
@@ -406,11 +501,17 @@ RowsGrid rows_grid(int64_t planes, int H, int W, int TH)
     return r;
 }
 
+// 3 x 3 windows: stride 1 with one column of padding, stride 2 with one or none; up to two rows of padding.
 bool rows_shape(int H, int W, int Ho, int Wo, int kh, int kw, int sh, int sw, int ph, int pw)
 {
-    if (kh != 3 || kw != 3 || sh != sw || (sh != 1 && sh != 2) || pw != 1 || ph < 0 || ph > 2) return false;
-    if ((W & 3) || W < 4 || H < 1) return false;
-    return sh == 1 ? Wo == W : Wo == W / 2;
+    if (kh != 3 || kw != 3 || sh != sw || (sh != 1 && sh != 2) || ph < 0 || ph > 2) return false;
+    if (pw != 1 && !(sh == 2 && pw == 0)) return false;
+    if (W < 4 || H < 1 || Wo < 1) return false;
+    return Wo == (W + 2 * pw - 3) / sh + 1;
+}
+bool k2s2_shape(int H, int W, int Ho, int Wo, int kh, int kw, int sh, int sw, int ph, int pw)
+{
+    return kh == 2 && kw == 2 && sh == 2 && sw == 2 && ph == 0 && pw == 0 && W >= 4 && H >= 2 && Wo == W / 2 && Ho == H / 2;
 }
 
 }  // namespace
@@ -419,27 +520,31 @@ hipError_t launch_maxpool2d_grad_rows(const float *x, const float *gy, float *gx
                                       int Wo, int kh, int kw, int sh, int sw, int ph, int pw, hipStream_t s, bool *taken)
 {
     *taken = false;
-    if (kh == 2 && kw == 2 && sh == 2 && sw == 2 && ph == 0 && pw == 0 && !(W & 3) && W >= 4 && H >= 2 && Wo == W / 2 &&
-        Ho == H / 2) {
-        constexpr int TH = 4;
-        const RowsGrid r = rows_grid(planes, H, W, TH);
-        if (!r.ok) return hipSuccess;
-        *taken = true;
-        hipLaunchKernelGGL((maxpool_grad_rows_k2s2_kernel<TH>), r.grid, dim3(kWave), 0, s, x, gy, gx, H, W, Ho, Wo, r.LPR, r.G,
-                           r.rcp, r.nstrips, planes);
-        return hipGetLastError();
-    }
-    if (!rows_shape(H, W, Ho, Wo, kh, kw, sh, sw, ph, pw)) return hipSuccess;
-    constexpr int TH1 = 4, TH2 = 4;
-    const RowsGrid r = rows_grid(planes, H, W, sh == 1 ? TH1 : TH2);
+    constexpr int TH = 4;
+    const bool rag = (W & 3) != 0;
+    const bool k2 = k2s2_shape(H, W, Ho, Wo, kh, kw, sh, sw, ph, pw);
+    if (!k2 && !rows_shape(H, W, Ho, Wo, kh, kw, sh, sw, ph, pw)) return hipSuccess;
+    const RowsGrid r = rows_grid(planes, H, W, TH);
     if (!r.ok) return hipSuccess;
     *taken = true;
-    if (sh == 1)
-        hipLaunchKernelGGL((maxpool_grad_rows_kernel<1, TH1>), r.grid, dim3(kWave), 0, s, x, gy, gx, H, W, Ho, Wo, ph, r.LPR,
-                           r.G, r.rcp, r.nstrips, planes);
-    else
-        hipLaunchKernelGGL((maxpool_grad_rows_kernel<2, TH2>), r.grid, dim3(kWave), 0, s, x, gy, gx, H, W, Ho, Wo, ph, r.LPR,
-                           r.G, r.rcp, r.nstrips, planes);
+#define SWS_MPG(S_, PW_, RAG_)                                                                                          \
+    hipLaunchKernelGGL((maxpool_grad_rows_kernel<S_, TH, PW_, RAG_>), r.grid, dim3(kWave), 0, s, x, gy, gx, H, W, Ho, Wo, ph, \
+                       r.LPR, r.G, r.rcp, r.nstrips, planes)
+    if (k2) {
+        if (rag)
+            hipLaunchKernelGGL((maxpool_grad_rows_k2s2_kernel<TH, true>), r.grid, dim3(kWave), 0, s, x, gy, gx, H, W, Ho, Wo,
+                               r.LPR, r.G, r.rcp, r.nstrips, planes);
+        else
+            hipLaunchKernelGGL((maxpool_grad_rows_k2s2_kernel<TH, false>), r.grid, dim3(kWave), 0, s, x, gy, gx, H, W, Ho, Wo,
+                               r.LPR, r.G, r.rcp, r.nstrips, planes);
+    } else if (sh == 1) {
+        if (rag) SWS_MPG(1, 1, true); else SWS_MPG(1, 1, false);
+    } else if (pw == 1) {
+        if (rag) SWS_MPG(2, 1, true); else SWS_MPG(2, 1, false);
+    } else {
+        if (rag) SWS_MPG(2, 0, true); else SWS_MPG(2, 0, false);
+    }
+#undef SWS_MPG
     return hipGetLastError();
 }
 
@@ -447,23 +552,29 @@ hipError_t launch_avgpool2d_grad_rows(const float *gy, float *gx, int64_t planes
                                       int kw, int sh, int sw, int ph, int pw, float scale, hipStream_t s, bool *taken)
 {
     *taken = false;
-    if (kh == 2 && kw == 2 && sh == 2 && sw == 2 && ph == 0 && pw == 0 && !(W & 3) && W >= 4 && H >= 2 && Wo == W / 2 &&
-        Ho == H / 2) {
-        constexpr int TH2 = 4;
-        const RowsGrid r = rows_grid(planes, H, W, TH2);
-        if (!r.ok) return hipSuccess;
-        *taken = true;
-        hipLaunchKernelGGL((avgpool_grad_rows_k2s2_kernel<TH2>), r.grid, dim3(kWave), 0, s, gy, gx, H, W, Ho, Wo, r.LPR, r.G,
-                           r.rcp, r.nstrips, planes, scale);
-        return hipGetLastError();
-    }
-    if (sh != 2 || !rows_shape(H, W, Ho, Wo, kh, kw, sh, sw, ph, pw)) return hipSuccess;
     constexpr int TH = 4;
+    const bool rag = (W & 3) != 0;
+    const bool k2 = k2s2_shape(H, W, Ho, Wo, kh, kw, sh, sw, ph, pw);
+    if (!k2 && (sh != 2 || !rows_shape(H, W, Ho, Wo, kh, kw, sh, sw, ph, pw))) return hipSuccess;
     const RowsGrid r = rows_grid(planes, H, W, TH);
     if (!r.ok) return hipSuccess;
     *taken = true;
-    hipLaunchKernelGGL((avgpool_grad_rows_s2_kernel<TH>), r.grid, dim3(kWave), 0, s, gy, gx, H, W, Ho, Wo, ph, r.LPR, r.G,
-                       r.rcp, r.nstrips, planes, scale);
+#define SWS_APG(PW_, RAG_)                                                                                              \
+    hipLaunchKernelGGL((avgpool_grad_rows_s2_kernel<TH, PW_, RAG_>), r.grid, dim3(kWave), 0, s, gy, gx, H, W, Ho, Wo, ph, r.LPR, \
+                       r.G, r.rcp, r.nstrips, planes, scale)
+    if (k2) {
+        if (rag)
+            hipLaunchKernelGGL((avgpool_grad_rows_k2s2_kernel<TH, true>), r.grid, dim3(kWave), 0, s, gy, gx, H, W, Ho, Wo, r.LPR,
+                               r.G, r.rcp, r.nstrips, planes, scale);
+        else
+            hipLaunchKernelGGL((avgpool_grad_rows_k2s2_kernel<TH, false>), r.grid, dim3(kWave), 0, s, gy, gx, H, W, Ho, Wo, r.LPR,
+                               r.G, r.rcp, r.nstrips, planes, scale);
+    } else if (pw == 1) {
+        if (rag) SWS_APG(1, true); else SWS_APG(1, false);
+    } else {
+        if (rag) SWS_APG(0, true); else SWS_APG(0, false);
+    }
+#undef SWS_APG
     return hipGetLastError();
 }
 

@@ -159,23 +159,27 @@ def test_avgpool2d_grad_argument_checks(B):
 ROW_PLANES = [(1, 1, 1, 4), (1, 3, 2, 8), (2, 5, 7, 12), (1, 9, 9, 60), (3, 3, 37, 112), (1, 2, 113, 256), (1, 17, 6, 20),
               (2, 2, 56, 56), (1, 1, 300, 16),
               # wider than a wavefront's 256 columns: strips (planes that end inside a strip, on a strip boundary, past one)
-              (1, 3, 21, 260), (1, 2, 9, 480), (1, 1, 14, 484), (1, 9, 6, 512), (1, 1, 5, 1000)]
+              (1, 3, 21, 260), (1, 2, 9, 480), (1, 1, 14, 484), (1, 9, 6, 512), (1, 1, 5, 1000),
+              # rows that are not a multiple of 4 long: the last lane holds 1, 2 or 3 columns; narrow planes and strips
+              (1, 3, 5, 5), (1, 1, 4, 6), (2, 2, 9, 7), (1, 2, 21, 111), (1, 1, 12, 149), (1, 3, 7, 254), (1, 2, 10, 255),
+              (1, 1, 11, 257), (1, 2, 8, 481), (1, 1, 9, 482), (1, 1, 6, 723), (1, 1, 5, 963)]
 
 
 @pytest.mark.parametrize("variant", [0, 128])
 @pytest.mark.parametrize("ph", [0, 1, 2])
-@pytest.mark.parametrize("stride", [1, 2])
+@pytest.mark.parametrize("stride,pw", [(1, 1), (2, 1), (2, 0)])
 @pytest.mark.parametrize("shape", ROW_PLANES)
-def test_row_streaming_maxpool_grad(B, shape, stride, ph, variant):
-    """3 x 3 windows, one column of padding, every row padding: plane counts that are not a multiple of 8,
-    heights that are not a multiple of the band, rows from one lane to a whole wavefront; random data
-    (no ties) within tolerance, and planes of few distinct values (ties everywhere) with integer
-    gradients bit for bit.  variant 128 runs the same cases on the band kernel."""
+def test_row_streaming_maxpool_grad(B, shape, stride, pw, ph, variant):
+    """3 x 3 windows, one column of padding (at stride 2 also none), every row padding: plane counts that are not a
+    multiple of 8, heights that are not a multiple of the band, rows from one lane to a whole wavefront and
+    beyond, rows that end inside a lane; random data (no ties) within tolerance, and planes of few distinct
+    values (ties everywhere) with integer gradients bit for bit.  variant 128 runs the same cases on the band
+    kernel."""
     h, wd = shape[2], shape[3]
     if 3 > h + 2 * ph:
         pytest.skip("window larger than plane")
-    geom = (3, 3, stride, stride, ph, 1)
-    ho, wo = (h + 2 * ph - 3) // stride + 1, (wd + 2 - 3) // stride + 1
+    geom = (3, 3, stride, stride, ph, pw)
+    ho, wo = (h + 2 * ph - 3) // stride + 1, (wd + 2 * pw - 3) // stride + 1
     r = np.random.Generator(np.random.PCG64(h * 1000 + wd + 7 * ph + stride))
     x = r.standard_normal(shape, dtype=np.float32)
     gy = r.standard_normal(shape[:2] + (ho, wo), dtype=np.float32)
@@ -183,8 +187,8 @@ def test_row_streaming_maxpool_grad(B, shape, stride, ph, variant):
     gi = workloads.integer_valued(shape[:2] + (ho, wo), -3, 3, h * wd)
     B.sws_set_option("pool2d_variant", variant)
     try:
-        _check(B, x, gy, geom, "rows max grad %s s%d ph%d" % (shape, stride, ph))
-        gx, ref = _check(B, xi, gi, geom, "rows max grad, ties %s s%d ph%d" % (shape, stride, ph))
+        _check(B, x, gy, geom, "rows max grad %s s%d ph%d pw%d" % (shape, stride, ph, pw))
+        gx, ref = _check(B, xi, gi, geom, "rows max grad, ties %s s%d ph%d pw%d" % (shape, stride, ph, pw))
     finally:
         B.sws_set_option("pool2d_variant", 0)
     assert np.array_equal(gx.astype(np.float64), ref)
@@ -193,21 +197,21 @@ def test_row_streaming_maxpool_grad(B, shape, stride, ph, variant):
 
 @pytest.mark.parametrize("variant", [0, 128])
 @pytest.mark.parametrize("ph", [0, 1, 2])
-@pytest.mark.parametrize("stride", [1, 2])
+@pytest.mark.parametrize("stride,pw", [(1, 1), (2, 1), (2, 0)])
 @pytest.mark.parametrize("shape", ROW_PLANES)
-def test_row_streaming_avgpool_grad(B, shape, stride, ph, variant):
+def test_row_streaming_avgpool_grad(B, shape, stride, pw, ph, variant):
     h, wd = shape[2], shape[3]
     if 3 > h + 2 * ph:
         pytest.skip("window larger than plane")
-    geom = (3, 3, stride, stride, ph, 1)
-    ho, wo = (h + 2 * ph - 3) // stride + 1, (wd + 2 - 3) // stride + 1
+    geom = (3, 3, stride, stride, ph, pw)
+    ho, wo = (h + 2 * ph - 3) // stride + 1, (wd + 2 * pw - 3) // stride + 1
     r = np.random.Generator(np.random.PCG64(h * 1000 + wd + 7 * ph + stride + 1))
     gy = r.standard_normal(shape[:2] + (ho, wo), dtype=np.float32)
     gi = workloads.integer_valued(shape[:2] + (ho, wo), -3, 3, h * wd + 1)
     B.sws_set_option("pool2d_variant", variant)
     try:
-        _check_avg(B, gy, h, wd, geom, 0, 1.0 / 9, "rows avg grad %s s%d ph%d" % (shape, stride, ph))
-        gx, ref = _check_avg(B, gi, h, wd, geom, 0, 0.5, "rows avg grad, integers %s s%d ph%d" % (shape, stride, ph))
+        _check_avg(B, gy, h, wd, geom, 0, 1.0 / 9, "rows avg grad %s s%d ph%d pw%d" % (shape, stride, ph, pw))
+        gx, ref = _check_avg(B, gi, h, wd, geom, 0, 0.5, "rows avg grad, integers %s s%d ph%d pw%d" % (shape, stride, ph, pw))
     finally:
         B.sws_set_option("pool2d_variant", 0)
     assert np.array_equal(gx.astype(np.float64), ref)
@@ -217,14 +221,14 @@ def test_row_streaming_adjoints_guard_band(B):
     """Nothing is written outside gx."""
     import torch
     r = np.random.Generator(np.random.PCG64(77))
-    for stride in (1, 2):
-      for wdt in (36, 500):
+    for k, stride, p in ((3, 1, 1), (3, 2, 1), (3, 2, 0), (2, 2, 0)):
+      for wdt in (36, 500, 37, 254, 501, 723):
         x = torch.from_numpy(r.standard_normal((3, 3, 21, wdt), dtype=np.float32)).cuda()
-        ho, wo = (21 + 2 - 3) // stride + 1, (wdt + 2 - 3) // stride + 1
+        ho, wo = (21 + 2 * p - k) // stride + 1, (wdt + 2 * p - k) // stride + 1
         gy = torch.from_numpy(r.standard_normal((3, 3, ho, wo), dtype=np.float32)).cuda()
         n = x.numel()
-        for fn in (lambda out: B.sws_maxpool2d_grad(x, gy, 3, 3, stride, stride, 1, 1, gx=out),
-                   lambda out: B.sws_avgpool2d_grad(gy, 21, wdt, 3, 3, stride, stride, 1, 1, scale=1 / 9, gx=out)):
+        for fn in (lambda out: B.sws_maxpool2d_grad(x, gy, k, k, stride, stride, p, p, gx=out),
+                   lambda out: B.sws_avgpool2d_grad(gy, 21, wdt, k, k, stride, stride, p, p, scale=1 / 9, gx=out)):
             buf = torch.full((n + 256,), 7.0, device="cuda")
             fn(buf[128:128 + n].view(3, 3, 21, wdt))
             torch.cuda.synchronize()
@@ -233,7 +237,10 @@ def test_row_streaming_adjoints_guard_band(B):
 
 @pytest.mark.parametrize("variant", [0, 128])
 @pytest.mark.parametrize("shape", [(1, 1, 2, 4), (2, 5, 7, 12), (1, 9, 9, 60), (3, 3, 37, 112), (1, 2, 112, 256), (1, 17, 6, 20),
-                                   (2, 2, 56, 56), (1, 3, 21, 260), (1, 2, 10, 480), (1, 1, 15, 1000)])
+                                   (2, 2, 56, 56), (1, 3, 21, 260), (1, 2, 10, 480), (1, 1, 15, 1000),
+                                   # rows that end inside a lane (odd widths: a last column without a window)
+                                   (1, 1, 4, 5), (1, 1, 4, 6), (1, 2, 9, 7), (2, 3, 21, 111), (1, 1, 12, 149), (1, 2, 6, 254),
+                                   (1, 1, 7, 257), (1, 1, 9, 482), (1, 1, 9, 723)])
 def test_row_streaming_maxpool_grad_2x2_stride_2(B, shape, variant):
     """2 x 2 windows at stride 2 without padding (windows do not overlap): odd heights (a last row without a window),
     narrow planes and strips; random data within tolerance, ties with integer gradients bit for bit, and the
@@ -258,7 +265,8 @@ def test_row_streaming_maxpool_grad_2x2_stride_2(B, shape, variant):
 
 @pytest.mark.parametrize("variant", [0, 128])
 @pytest.mark.parametrize("shape", [(1, 1, 2, 4), (2, 5, 7, 12), (3, 3, 37, 112), (1, 2, 112, 256), (2, 2, 56, 56), (1, 3, 21, 260),
-                                   (1, 1, 15, 1000)])
+                                   (1, 1, 15, 1000), (1, 1, 4, 5), (1, 1, 4, 6), (1, 2, 9, 7), (2, 3, 21, 111), (1, 1, 12, 149),
+                                   (1, 2, 6, 254), (1, 1, 7, 257), (1, 1, 9, 482), (1, 1, 9, 723)])
 def test_row_streaming_avgpool_grad_2x2_stride_2(B, shape, variant):
     h, wd = shape[2], shape[3]
     geom = (2, 2, 2, 2, 0, 0)
