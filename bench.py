@@ -356,7 +356,16 @@ def sweeps_table(torch, B, workloads, iters=20):
     ms = time_launches(torch, lambda: B.sws_pool2d(1, xr_, 3, 3, 1, 1, 1, 1, 1.0, y=yr_), iters)
     out["wide_planes"]["111x111_max_3x3_s1"] = {"us": round(ms * 1e3, 2), "GBps": round(8.0 * xr_.numel() / ms / 1e6, 1),
                                                 "frac_hbm": round(8.0 * xr_.numel() / ms / 1e6 / HBM_PEAK_GBPS, 4)}
-    del xr_, yr_
+    gyr_ = torch.empty(32, 64, 56, 56, device="cuda").normal_()
+    gxr_ = torch.empty_like(xr_)
+    for name, fn, nb in (("111x111_maxpool3x3_s1_grad", lambda: B.sws_maxpool2d_grad(xr_, yr_, 3, 3, 1, 1, 1, 1, gx=gxr_),
+                          12.0 * xr_.numel()),
+                         ("111x111_maxpool3x3_s2_grad", lambda: B.sws_maxpool2d_grad(xr_, gyr_, 3, 3, 2, 2, 1, 1, gx=gxr_),
+                          4.0 * (2 * xr_.numel() + gyr_.numel()))):
+        ms = time_launches(torch, fn, iters)
+        out["wide_planes"][name] = {"us": round(ms * 1e3, 2), "GBps": round(nb / ms / 1e6, 1),
+                                    "frac_hbm": round(nb / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+    del xr_, yr_, gyr_, gxr_
     x3b = torch.empty(32, 64, 112, 112, device="cuda").uniform_(-1, 1)
     gy3b = torch.empty(32, 64, 56, 56, device="cuda").normal_()
     gx3b = torch.empty_like(x3b)
