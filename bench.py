@@ -918,21 +918,20 @@ def main():
             rec["GFLOPs"] = round(fl / ms / 1e6, 1)
         kernels[name] = rec
 
-    # dominant kernel: the one the step spends most time in.  The four launches with w = 64 and 255 run the scan
-    # kernel (slide_scan_kernel), the two with w = 16 the strips-in-registers kernel (slide_reg_kernel), the
-    # depthwise convolution the thin-channel kernel.
-    scan = [i for i, l in enumerate(launches[:6]) if not l[0].endswith("_w16")]
-    reg = [i for i, l in enumerate(launches[:6]) if l[0].endswith("_w16")]
+    # dominant kernel: the one the step spends most time in.  The six sliding-sum launches run the scan kernel
+    # (slide_scan_kernel; on inputs of this size with streamed loads for w = 16 and 64), the depthwise convolution
+    # the thin-channel kernel.
+    scan = list(range(6))
     for i, l in enumerate(launches):
-        kernels[l[0]]["kernel"] = "slide_scan_kernel" if i in scan else ("slide_reg_kernel" if i in reg else "conv1d_thin_kernel")
+        kernels[l[0]]["kernel"] = "slide_scan_kernel" if i in scan else "conv1d_thin_kernel"
     scan_ms = sum(per[i] for i in scan)
     slide_ms = sum(per[:6])
-    if scan_ms >= per[6] and scan_ms >= sum(per[i] for i in reg):
-        dom_name = "slide_scan_kernel (sws_slide1d, w in {64,255}, add and max)"
+    if scan_ms >= per[6]:
+        dom_name = "slide_scan_kernel (sws_slide1d, w in {16,64,255}, add and max)"
         dom_bytes = sum(launches[i][2] for i in scan) / len(scan)
         dom_ms = scan_ms / len(scan)
-        t64, t255 = read_traffic("slide_scan_cfg5_w64_hbm_traffic.txt"), read_traffic("slide_scan_cfg5_w255_hbm_traffic.txt")
-        traffic = (t64 + t255) / 2.0 if t64 and t255 else None
+        ts = [read_traffic("slide_scan_cfg5_w%d_hbm_traffic.txt" % w) for w in (16, 64, 255)]
+        traffic = sum(ts) / 3.0 if all(ts) else None
     else:
         dom_name = "depthwise conv kernel (sws_conv1d, k=31, groups=128)"
         dom_bytes = launches[6][2]

@@ -185,7 +185,7 @@ __global__ __launch_bounds__(WPW * kWave) void slide_scan_kernel(const float *__
     __shared__ __attribute__((aligned(16))) float lds[WPW * 2 * REGION];
 
     // kernel flag bits: 2 = non-temporal stores, 4 = aligned tile origins, 32 = workgroups keep
-    // their launch order instead of the XCD-contiguous mapping
+    // their launch order instead of the XCD-contiguous mapping, 64-256 (a number) = which strips are loaded streamed
     const int64_t unit = (flags & 32) ? (int64_t)blockIdx.x : xcd_unit(n_units);
     if (unit < 0) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -253,11 +253,26 @@ __global__ __launch_bounds__(WPW * kWave) void slide_scan_kernel(const float *__
         // ---- stage the tile: coalesced strips -> LDS; boundary rule in the padding, identity
         //      outside the extended row
         if (t0 - pad_left >= 0 && t0 - pad_left <= len - N) {
-#pragma unroll
-            for (int j = 0; j < NS; ++j) {
-                const int q = j * 256 + 4 * lane;
-                *(v4f *)(A + strip_pos + 256 * j) = *(const v4f_u *)(xt + q);
-            }
+            // flags bits 6-8: which strips are loaded streamed (non-temporal): 4 = all (the launcher's choice for
+            // large inputs and windows up to 129 / 173), 3 = all but the last, 2 = the middle two, 1 = the second,
+            // 0 = none.  Streaming all strips but those that reach into a neighbouring tile's inputs gains half as
+            // much where streaming gains and loses half as much where it loses.  One loop per choice: with a
+            // per-strip test, or with two branches that differ in nothing else, the compiler merges the loads of
+            // a strip into a plain one.
+            const int n_stream = (flags >> 6) & 7;
+#define SWS_STAGE(MASK_)                                                                                        \
+    _Pragma("unroll") for (int j = 0; j < NS; ++j)                                                              \
+    {                                                                                                           \
+        const int q = j * 256 + 4 * lane;                                                                       \
+        if ((MASK_ >> j) & 1) *(v4f *)(A + strip_pos + 256 * j) = __builtin_nontemporal_load((const v4f_u *)(xt + q)); \
+        else *(v4f *)(A + strip_pos + 256 * j) = *(const v4f_u *)(xt + q);                                      \
+    }
+            if (n_stream == 4) { SWS_STAGE(15) }
+            else if (n_stream == 3) { SWS_STAGE(7) }
+            else if (n_stream == 2) { SWS_STAGE(6) }
+            else if (n_stream == 1) { SWS_STAGE(2) }
+            else { SWS_STAGE(0) }
+#undef SWS_STAGE
         } else {
             // a tile at an end of its row: strip by strip (wave-uniform tests) — whole strips inside
             // the row are still 128-bit loads, strips wholly outside hold the identity
@@ -464,10 +479,11 @@ hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, 
     // single-wavefront workgroups measure a little faster on large plain inputs where the halo is
     // small or the scan is the slower one (x[32768,16384], TB/s, one / four wavefronts: w = 16 + 6.05 /
     // 5.94, max 5.98 / 5.92; w = 64 equal; w = 255 max 5.87 / 5.77, + with one tile per workgroup in
-    // launch order 6.10 / 5.90).  Option slide_chunk bit 64 forces them, bit 128 the four-wavefront shape.
+    // launch order 6.10 / 5.90; beyond w = 320 + is faster in the four-wavefront shape again: w = 400 0.79 against
+    // 0.84 ms, w = 700 1.21 against 1.38).  Option slide_chunk bit 64 forces them, bit 128 the four-wavefront shape.
     const bool plain = !chain && lv == len;
     const bool big = rows * (int64_t)tiles >= 16384;
-    const bool single = plain && !(opt & 128) && ((opt & 64) || (big && (S <= 32 || S > 172)));
+    const bool single = plain && !(opt & 128) && ((opt & 64) || (big && (S <= 32 || (S > 172 && (OP != SWS_OP_ADD || S <= 320)))));
     const int wpw = single ? 1 : kWavesPerWg;
     int64_t g = one_tile ? wpw : 2 * wpw;
     bool remap = one_tile;
@@ -476,6 +492,12 @@ hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, 
     if (opt & 4) remap = true;
     if (opt & 8) remap = false;
     if (!remap) flags |= 32;
+    // Inputs far beyond the caches are streamed while the halo is small (x[32768,16384], ms per launch, plain /
+    // streamed loads: w = 16 0.725 / 0.661, 32 0.708 / 0.658, 64 0.709 / 0.677, 128 + 0.702 / 0.679, max 0.745 /
+    // 0.714, 173 + 0.712 / 0.693, max level; beyond that streaming loses: w = 200 0.73 / 0.76-0.79, 255 0.71 / 0.80).
+    // slide_chunk bit 256: plain loads.
+    if (plain && rows * (int64_t)len >= ((int64_t)1 << 27) && !(opt & 256) && (S <= 128 || (OP == SWS_OP_ADD && S <= 172)))
+        flags |= 4 << 6;
     const int64_t n_units = (n_tiles + g - 1) / g;
     const int64_t grid = remap ? xcd_grid(n_units) : n_units;
     if (grid > 2147483647LL) return kNotTaken;
@@ -548,6 +570,7 @@ hipError_t launch_chain_padded(const float *x, float *y, int64_t rows, int len, 
     return hipSuccess;
 }
 
+constexpr int kStreamMinLen = 4096;                 // rows from this length on: large inputs go to the scan kernel's streamed loads
 constexpr int kDirectMaxW = 11;                      // widest window of the shifted-load kernel (four 128-bit loads per lane)
 constexpr int kScanMaxW = kWave * 16 - 64 + 1;      // leaves at least 64 outputs per wave tile
 constexpr int kLongMinW = 449;                      // from here the long-window kernel beats the scan kernel (16384-long rows: w = 400 level, 512 1.1-1.4 x, 850 3 x)
@@ -579,8 +602,12 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
         // (x[32768,16384], w = 2 .. 9: 6.1-6.4 TB/s against 5.9-6.0).
         // (Strips against the scan kernel there, TB/s: w = 10 6.07 / 5.85, w = 12 6.01 / 5.96, w = 16 4.7 / 5.96 —
         // beyond four 128-bit loads per lane the re-reads through L1 cost more than the scan's LDS passes.)
-        const bool small_w = (w <= 9 && (lo <= 8192 || rows * len64 <= (8LL << 20))) ||
-                             (w <= kDirectMaxW && rows * (int64_t)lo >= (1LL << 24));
+        // (Of the large inputs only w <= 4 and w = 9 stay here: the strips-in-registers kernel below measured level
+        // or ahead for the other windows at every row length — x of 2^29 elements, ms, shifted loads / registers:
+        // w = 5 rows of 1024 0.767 / 0.709, 2048 0.731 / 0.675, 8192 0.728 / 0.680, 65536 0.702 / 0.698; w = 11 rows of
+        // 2048 1.04 / 0.70, 8192 0.83 / 0.675, 65536 level; w = 9 level everywhere.)
+        const bool big_out = rows * (int64_t)lo >= (1LL << 24);
+        const bool small_w = (w <= 9 && (lo <= 8192 || rows * len64 <= (8LL << 20))) || ((w <= 4 || w == 9) && big_out);
         // Rows too short for either: up to 256 outputs (one strip of the shifted-load kernel, a
         // quarter of the scan's wave tile) the short-row kernel for every window it has, several
         // rows per wavefront; up to 1024 outputs for the windows the shifted loads do not take.
@@ -591,18 +618,33 @@ hipError_t launch_slide1d(int op, const float *x, float *y, int64_t rows, int64_
         // more as w grows (mirror, max, TB/s, short-row kernel / scan): rows of 56 5.5-1.4 / 0.4 for
         // w = 3 .. 33; 224 5.6-2.4 / 1.6 up to w = 16, 1.4 / 1.6 at 33; 1024 5.8-3.9 / 3.5 up to 16;
         // 2048 5.7-5.4 / 4.8-4.6 up to 9, 3.8 / 4.6 at 16.
+        const bool streamed = !padded && w >= 2 && rows * len64 >= (1LL << 27) && len64 >= kStreamMinLen;
         const bool short_rows = w <= slide1d_rows_max_w() &&
                                 (padded ? (lo <= 128 || (w <= 16 && lo <= 1024) || (w <= 9 && lo <= 2048))
                                         : (lo <= 256 || (w > 9 && lo <= 1024)));
-        if (short_rows) variant = 7;
+        // A row that is exactly one tile of the scan kernel (1024-long rows with w - 1 a multiple of 16: all its
+        // outputs in one aligned tile): x[524288,1024], w = 17 0.66 ms against 0.70 on the short-row kernel, w = 33
+        // 0.65 against 0.98.
+        const int tout1 = (kWave * 16 - (w - 1)) & ~15;
+        const bool one_tile_rows = !padded && w > 16 && w < kLongMinW && lo > 768 && lo + max_origin_shift(lo, 16) <= tout1;
+        if (one_tile_rows) variant = 3;
+        else if (short_rows) variant = 7;
         else if (w == 1) variant = padded ? 1 : 2;
         else if (padded && pad_mode == SWS_PAD_SHRINK) variant = w <= kScanMaxW ? 3 : 1;   // one pass rescales by the real elements
         else if (padded) variant = w < kLongMinW ? 3 : (w <= kLongMaxW ? 8 : 6);   // 6: a chain over extended rows
+        // Inputs far beyond the caches on long rows: the scan kernel loads streamed there (launch_scan) and is then
+        // the fastest for nearly every small window too.  x[32768,16384], ms per launch, scan / the kernels below:
+        // + w = 2 .. 8 0.656-0.660 / 0.688-0.706, 9 0.667 / 0.673, 10 0.661 / 0.702, 11 0.661 / 0.745, 12 .. 16
+        // 0.662 / 0.681, 17 level; max w = 2 .. 8 0.673-0.678 / 0.694-0.708, 9 0.687 / 0.673, 10 0.681 / 0.703,
+        // 11 0.683 / 0.741, 12 .. 16 level, 17 0.701 / 0.675.
+        else if (streamed && w <= kDirectMaxW && !(w == 9 && op != SWS_OP_ADD)) variant = 3;
+        else if (streamed && w >= 12 && w <= 16) variant = 3;
+        // Large inputs, w = 5 .. 17 except 9: one strip per wavefront held in registers (strips overlap by 16 elements).
+        // Measured on x[32768,16384], ms per 2 GiB, that kernel / the scan with plain loads: max 0.700-0.711 / 0.738,
+        // + 0.699-0.703 / 0.710-0.715; from w = 18 the overlap is 32 elements and + loses (0.73 / 0.714), max gains
+        // under 1.5 %.
+        else if (w >= slide1d_reg_min_w() && w <= 17 && w != 9 && big_out) variant = 9;
         else if (small_w) variant = 2;
-        // Windows 12 .. 17 on large inputs: one strip per wavefront held in registers (strips overlap by 16 elements).
-        // Measured on x[32768,16384], ms per 2 GiB, that kernel / the scan: max 0.700-0.711 / 0.738, + 0.699-0.703 /
-        // 0.710-0.715; from w = 18 the overlap is 32 elements and + loses (0.73 / 0.714), max gains under 1.5 %.
-        else if (w >= 12 && w <= 17 && rows * (int64_t)lo >= (1LL << 24)) variant = 9;
         else variant = w < kLongMinW ? 3 : (w <= kLongMaxW ? 8 : 5);
     }
     if (variant == 8) {
