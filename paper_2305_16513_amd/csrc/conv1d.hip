@@ -41,7 +41,8 @@ __host__ __device__ constexpr int lds_pos(int q) { return q + 4 * (q >> 4); }
 
 // RULE: the row is extended by `pad` elements in front and p_hi - L behind under the boundary rule
 // `pmode` (mirror, periodic, edge) instead of zeros; only the tiles at the ends of a row differ.
-template <int KB4, bool RULE>
+// STREAM: the tiles' strips are loaded streamed (non-temporal) — inputs far beyond the caches.
+template <int KB4, bool RULE, bool STREAM = false>
 __global__ __launch_bounds__(kThreads, (KB4 <= 8 ? 5 : 4)) void conv1d_thin_kernel(
     const float *__restrict__ x, const float *__restrict__ wgt, float *__restrict__ y, int L, int Lo, int k,
     int pad, int Cin, int Cout, int cog, int tiles_per_row, int group, int chunks_per_row, int64_t n_units,
@@ -85,8 +86,17 @@ __global__ __launch_bounds__(kThreads, (KB4 <= 8 ? 5 : 4)) void conv1d_thin_kern
     auto load_tile = [&](int t, v4f (&g)[5]) {
         const int p0 = t * kTileOut - c - pad;
         if (p0 >= 0 && p0 <= L - NI) {
+            // (streamed loads on inputs far beyond the caches, as in the sliding-sum scan kernel; the halo strip, which
+            // the next tile reads again, stays a plain load)
+            // (A template parameter: two run-time branches that differ in nothing but the hint are merged by the
+            // compiler into plain loads.)
+            if constexpr (STREAM) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) g[j] = *(const v4f_u *)(xr + p0 + j * 256 + 4 * lane);
+                for (int j = 0; j < 4; ++j) g[j] = __builtin_nontemporal_load((const v4f_u *)(xr + p0 + j * 256 + 4 * lane));
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) g[j] = *(const v4f_u *)(xr + p0 + j * 256 + 4 * lane);
+            }
             g[4] = (4 * lane < K4) ? *(const v4f_u *)(xr + p0 + kTileOut + 4 * lane) : (v4f){0.0f, 0.0f, 0.0f, 0.0f};
         } else {
             // a tile at an end of its row: strip by strip (wave-uniform tests) — whole strips inside
@@ -184,6 +194,9 @@ hipError_t launch_thin(const float *x, const float *wgt, float *y, int64_t rows_
     const int tiles_per_row = (Lo + max_origin_shift(Lo, 16) + kTileOut - 1) / kTileOut;     // origins move back
     // Tiles per workgroup (measured): two per wavefront while HBM is the bound (the tiles in flight
     // stay a compact window of memory), many once the FMAs dominate (k > 32: fewer prologues).
+    // (With streamed loads four per wavefront measured 2.5 % faster when the layer's launches follow each other, 0.833
+    // against 0.855 ms on cfg 5's k = 31 layer, but 1 % slower between other kernels, 0.779 against 0.771: not taken.)
+    const bool stream = !RULE && rows_out * (int64_t)L >= ((int64_t)1 << 27) && !(g_opt.slide_chunk & 256);
     int64_t g = (KB4 <= 8 ? 2 : 16) * kWavesPerWg;
     if (g_opt.slide_group > 0) g = g_opt.slide_group;
     if (g > tiles_per_row) g = tiles_per_row;
@@ -192,6 +205,14 @@ hipError_t launch_thin(const float *x, const float *wgt, float *y, int64_t rows_
     const int64_t n_units = rows_out * chunks_per_row;
     const int64_t grid = xcd_grid(n_units);
     if (grid > 2147483647LL) return kNotTaken;
+    // inputs far beyond the caches are loaded streamed (slide_chunk bit 256: plain loads, as for the sliding sums)
+    if constexpr (!RULE) {
+        if (stream) {
+            hipLaunchKernelGGL((conv1d_thin_kernel<KB4, false, true>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, wgt, y, L,
+                               Lo, k, pad, Cin, Cout, cog, tiles_per_row, group, chunks_per_row, n_units, wflip, p_hi, pmode);
+            return hipGetLastError();
+        }
+    }
     hipLaunchKernelGGL((conv1d_thin_kernel<KB4, RULE>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, wgt, y, L, Lo, k,
                        pad, Cin, Cout, cog, tiles_per_row, group, chunks_per_row, n_units, wflip, p_hi, pmode);
     return hipGetLastError();

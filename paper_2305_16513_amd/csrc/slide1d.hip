@@ -156,7 +156,7 @@ template <> struct SegStep<SWS_OP_MIN> {
 // MODE 0: plain rows.  MODE 1: rows extended by a boundary rule.  MODE 2: one link of a chain of
 // windows (see launch_chain): rows `pitch` apart of which `len` elements are used, results
 // combined with what an earlier link left in y.
-template <int OP, int C, int MODE, int WPW = kWavesPerWg>
+template <int OP, int C, int MODE, int WPW = kWavesPerWg, bool STREAM = false>
 __global__ __launch_bounds__(WPW * kWave) void slide_scan_kernel(const float *__restrict__ x,
                                                               float *__restrict__ y, int len, int lo, int S,
                                                               float scale, int tiles_per_row, int tout,
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(WPW * kWave) void slide_scan_kernel(const float *__
     __shared__ __attribute__((aligned(16))) float lds[WPW * 2 * REGION];
 
     // kernel flag bits: 2 = non-temporal stores, 4 = aligned tile origins, 32 = workgroups keep
-    // their launch order instead of the XCD-contiguous mapping, 64-256 (a number) = which strips are loaded streamed
+    // their launch order instead of the XCD-contiguous mapping
     const int64_t unit = (flags & 32) ? (int64_t)blockIdx.x : xcd_unit(n_units);
     if (unit < 0) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -253,26 +253,16 @@ __global__ __launch_bounds__(WPW * kWave) void slide_scan_kernel(const float *__
         // ---- stage the tile: coalesced strips -> LDS; boundary rule in the padding, identity
         //      outside the extended row
         if (t0 - pad_left >= 0 && t0 - pad_left <= len - N) {
-            // flags bits 6-8: which strips are loaded streamed (non-temporal): 4 = all (the launcher's choice for
-            // large inputs and windows up to 129 / 173), 3 = all but the last, 2 = the middle two, 1 = the second,
-            // 0 = none.  Streaming all strips but those that reach into a neighbouring tile's inputs gains half as
-            // much where streaming gains and loses half as much where it loses.  One loop per choice: with a
-            // per-strip test, or with two branches that differ in nothing else, the compiler merges the loads of
-            // a strip into a plain one.
-            const int n_stream = (flags >> 6) & 7;
-#define SWS_STAGE(MASK_)                                                                                        \
-    _Pragma("unroll") for (int j = 0; j < NS; ++j)                                                              \
-    {                                                                                                           \
-        const int q = j * 256 + 4 * lane;                                                                       \
-        if ((MASK_ >> j) & 1) *(v4f *)(A + strip_pos + 256 * j) = __builtin_nontemporal_load((const v4f_u *)(xt + q)); \
-        else *(v4f *)(A + strip_pos + 256 * j) = *(const v4f_u *)(xt + q);                                      \
-    }
-            if (n_stream == 4) { SWS_STAGE(15) }
-            else if (n_stream == 3) { SWS_STAGE(7) }
-            else if (n_stream == 2) { SWS_STAGE(6) }
-            else if (n_stream == 1) { SWS_STAGE(2) }
-            else { SWS_STAGE(0) }
-#undef SWS_STAGE
+            // STREAM: streamed (non-temporal) loads, the launcher's choice for large inputs and windows up to 129 /
+            // 173.  (Streaming all strips but those that reach into a neighbouring tile's inputs gains half as much
+            // where streaming gains and loses half as much where it loses.  A template parameter: run-time branches
+            // that differ in nothing but the hint are merged by the compiler into plain loads.)
+#pragma unroll
+            for (int j = 0; j < NS; ++j) {
+                const int q = j * 256 + 4 * lane;
+                if constexpr (STREAM) *(v4f *)(A + strip_pos + 256 * j) = __builtin_nontemporal_load((const v4f_u *)(xt + q));
+                else *(v4f *)(A + strip_pos + 256 * j) = *(const v4f_u *)(xt + q);
+            }
         } else {
             // a tile at an end of its row: strip by strip (wave-uniform tests) — whole strips inside
             // the row are still 128-bit loads, strips wholly outside hold the identity
@@ -496,8 +486,9 @@ hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, 
     // streamed loads: w = 16 0.725 / 0.661, 32 0.708 / 0.658, 64 0.709 / 0.677, 128 + 0.702 / 0.679, max 0.745 /
     // 0.714, 173 + 0.712 / 0.693, max level; beyond that streaming loses: w = 200 0.73 / 0.76-0.79, 255 0.71 / 0.80).
     // slide_chunk bit 256: plain loads.
+    bool stream = false;
     if (plain && rows * (int64_t)len >= ((int64_t)1 << 27) && !(opt & 256) && (S <= 128 || (OP == SWS_OP_ADD && S <= 172)))
-        flags |= 4 << 6;
+        stream = true;
     const int64_t n_units = (n_tiles + g - 1) / g;
     const int64_t grid = remap ? xcd_grid(n_units) : n_units;
     if (grid > 2147483647LL) return kNotTaken;
@@ -512,6 +503,12 @@ hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, 
     } else if (lv != len) {
         hipLaunchKernelGGL((slide_scan_kernel<OP, C, 1>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
                            S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, pad_left, pad_mode, lv);
+    } else if (single && stream) {
+        hipLaunchKernelGGL((slide_scan_kernel<OP, C, 0, 1, true>), dim3((unsigned)grid), dim3(kWave), 0, s, x, y, len, lo,
+                           S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, 0, 0, len);
+    } else if (stream) {
+        hipLaunchKernelGGL((slide_scan_kernel<OP, C, 0, kWavesPerWg, true>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y,
+                           len, lo, S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, 0, 0, len);
     } else if (single) {
         hipLaunchKernelGGL((slide_scan_kernel<OP, C, 0, 1>), dim3((unsigned)grid), dim3(kWave), 0, s, x, y, len, lo,
                            S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, 0, 0, len);
