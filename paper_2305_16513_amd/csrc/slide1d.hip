@@ -477,7 +477,9 @@ hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, 
     const int wpw = single ? 1 : kWavesPerWg;
     int64_t g = one_tile ? wpw : 2 * wpw;
     bool remap = one_tile;
-    if (single && OP == SWS_OP_ADD && S > 172) g = 1;
+    // one tile per workgroup for 172 < S <= 320, max / min too: with two, 1.17 x the input came from HBM (counters,
+    // max w = 255) against 1.04 x with one, and the bench step's max w = 255 launch went from 0.725 to 0.705 ms
+    if (single && S > 172 && S <= 320) g = 1;
     if (g_opt.slide_group > 0) g = (g_opt.slide_group + wpw - 1) / wpw * wpw;
     if (opt & 4) remap = true;
     if (opt & 8) remap = false;
