@@ -489,7 +489,7 @@ hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, 
     // 0.714, 173 + 0.712 / 0.693, max level; beyond that streaming loses: w = 200 0.73 / 0.76-0.79, 255 0.71 / 0.80).
     // slide_chunk bit 256: plain loads.
     bool stream = false;
-    if (plain && rows * (int64_t)len >= ((int64_t)1 << 27) && !(opt & 256) && (S <= 128 || (OP == SWS_OP_ADD && S <= 172)))
+    if (!chain && rows * (int64_t)len >= ((int64_t)1 << 27) && !(opt & 256) && (S <= 128 || (OP == SWS_OP_ADD && S <= 172)))
         stream = true;
     const int64_t n_units = (n_tiles + g - 1) / g;
     const int64_t grid = remap ? xcd_grid(n_units) : n_units;
@@ -502,6 +502,9 @@ hipError_t launch_scan(const float *x, float *y, int64_t rows, int len, int lo, 
         if (!(chain & 2)) flags &= ~2;                // y is read again by the next link: plain stores
         hipLaunchKernelGGL((slide_scan_kernel<OP, C, 2>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
                            S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, 0, chain & 1, pitch);
+    } else if (lv != len && stream) {                 // (the tiles at the ends of a row stage strip by strip, plainly)
+        hipLaunchKernelGGL((slide_scan_kernel<OP, C, 1, kWavesPerWg, true>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y,
+                           len, lo, S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, pad_left, pad_mode, lv);
     } else if (lv != len) {
         hipLaunchKernelGGL((slide_scan_kernel<OP, C, 1>), dim3((unsigned)grid), dim3(kThreads), 0, s, x, y, len, lo,
                            S, scale, tiles, tout, (int)g, n_tiles, n_units, flags, pad_left, pad_mode, lv);
