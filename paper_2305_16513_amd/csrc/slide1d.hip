@@ -7,8 +7,8 @@
 //    vector is the (+) of w shifted copies of the input vector.  A lane owns four consecutive
 //    outputs and reads its shifted operands as 128-bit loads at +4, +8, +12 elements.  Two launch
 //    shapes: 1024-output tiles, four wavefronts per workgroup (w <= 9 on short rows or small
-//    problems), and 256-output strips, one wavefront per workgroup (w <= 11 on large inputs, where
-//    it beats the scan below by 3-6 %; in the tile shape the scan is the faster one there).
+//    problems), and 256-output strips, one wavefront per workgroup (large inputs: w <= 4 and w = 9
+//    where the scan below does not load streamed, max / min at w = 9 where it does).
 //    Also w = 1 (a scaled copy).
 //
 //  * slide_scan_kernel (every w >= 2): the block form of the Vector Input algorithm
